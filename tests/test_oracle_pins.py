@@ -1,0 +1,418 @@
+"""Pins for the CPU oracle: each test fixes it to something other than itself
+(hand-computed sums, library routines on the exact-product table, closed forms).
+
+The paper (arXiv 2203.04071) prints no worked numeric example, so no expected
+value here comes from the paper's tables; the pins are what the definitions in
+Sec. III-A (affine quantiser), III-B (layers), III-C (table = 1:1 image of the
+multiplier) and IV (every product is one table entry) fix mathematically.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+from paper_2203_04071_amd import workloads as wl
+
+# a 2-bit multiplier table written out by hand: rows a = -2,-1,0,1; columns w = -2,-1,0,1.
+# Not symmetric, and the zero-activation row is not zero.
+T2 = np.array([[5, 2, 0, -3],
+               [1, 1, -1, -1],
+               [7, 0, 0, 0],
+               [-2, -1, 4, 1]], dtype=np.int32)
+
+
+def test_linear_hand_computed():
+    A = np.array([[-2, 1, 0], [1, 1, -1]], dtype=np.int8)
+    W = np.array([[0, -1, 1], [-2, -2, 1]], dtype=np.int8)
+    # acc[0][0] = T[-2][0] + T[1][-1] + T[0][1] = 0 - 1 + 0
+    # acc[0][1] = T[-2][-2] + T[1][-2] + T[0][1] = 5 - 2 + 0
+    # acc[1][0] = T[1][0] + T[1][-1] + T[-1][1] = 4 - 1 - 1
+    # acc[1][1] = T[1][-2] + T[1][-2] + T[-1][1] = -2 - 2 - 1
+    want = np.array([[-1, 3], [2, -5]], dtype=np.int32)
+    assert (orc.approx_linear(T2, 2, A, W) == want).all()
+
+
+def test_conv_hand_computed_padding_is_looked_up():
+    x = np.array([1, -2], dtype=np.int8).reshape(1, 1, 1, 2)
+    w = np.array([-2, 1], dtype=np.int8).reshape(1, 1, 1, 2)
+    # pad 1 left/right: out[0] = T[0][-2] + T[1][1] = 7 + 1 ; out[1] = T[1][-2] + T[-2][1] = -2 - 3 ;
+    # out[2] = T[-2][-2] + T[0][1] = 5 + 0
+    want = np.array([8, -5, 5], dtype=np.int32).reshape(1, 1, 1, 3)
+    for form in ("direct", "im2col"):
+        got = orc.approx_conv2d(T2, 2, x, w, (1, 1), (0, 1), form=form)
+        assert (got == want).all(), form
+
+
+def test_conv_transpose_hand_computed():
+    x = np.array([1, -2], dtype=np.int8).reshape(1, 1, 1, 2)
+    w = np.array([-2, 1], dtype=np.int8).reshape(1, 1, 1, 2)
+    # stride 2: outputs never overlap: T[1][-2], T[1][1], T[-2][-2], T[-2][1]
+    got = orc.approx_conv_transpose2d(T2, 2, x, w, 2, 0)
+    assert got.reshape(-1).tolist() == [-2, 1, 5, -3]
+    # stride 1: the middle output sums two real pairs, the ends one each
+    got = orc.approx_conv_transpose2d(T2, 2, x, w, 1, 0)
+    assert got.reshape(-1).tolist() == [-2, 1 + 5, -3]
+
+
+@pytest.mark.parametrize("bits", [2, 4, 6, 7, 8])
+def test_exact_table_is_integer_gemm(bits):
+    rng = np.random.default_rng(bits)
+    M, K, N = 7, 33, 5
+    A = wl.random_i8(rng, (M, K), bits)
+    W = wl.random_i8(rng, (N, K), bits)
+    want = A.astype(np.int64) @ W.astype(np.int64).T
+    assert (orc.approx_linear(wl.exact_lut(bits), bits, A, W) == want).all()
+
+
+CONV_CASES = [
+    # N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, groups
+    (2, 3, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, 1, 1),
+    (1, 4, 9, 7, 6, 3, 3, 2, 2, 1, 1, 1, 1, 1),
+    (2, 2, 6, 10, 3, 1, 1, 1, 1, 0, 0, 1, 1, 1),
+    (1, 3, 7, 7, 2, 5, 3, 2, 1, 2, 0, 1, 1, 1),
+    (1, 4, 8, 8, 8, 3, 3, 1, 1, 2, 2, 2, 2, 2),
+    (2, 6, 5, 5, 6, 3, 3, 1, 1, 1, 1, 1, 1, 6),
+    (1, 2, 4, 4, 3, 4, 4, 1, 1, 3, 3, 1, 1, 1),
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_exact_table_is_library_conv2d(case):
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, g = case
+    rng = np.random.default_rng(sum(case))
+    x = wl.random_i8(rng, (N, Cin, H, W), 8)
+    w = wl.random_i8(rng, (Cout, Cin // g, kh, kw), 8)
+    want = torch.nn.functional.conv2d(torch.from_numpy(x.astype(np.float64)), torch.from_numpy(w.astype(np.float64)),
+                                      stride=(sh, sw), padding=(ph, pw), dilation=(dh, dw), groups=g).numpy()
+    ex = wl.exact_lut(8)
+    for form in ("direct", "im2col"):
+        got = orc.approx_conv2d(ex, 8, x, w, (sh, sw), (ph, pw), (dh, dw), g, form=form)
+        assert got.shape == want.shape
+        assert (got.astype(np.float64) == want).all(), form
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_direct_equals_expanded_matrix_product(case):
+    """Conv == (expanded input matrix) x (filter matrix), on an arbitrary table (Sec. III-B)."""
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, g = case
+    rng = np.random.default_rng(1 + sum(case))
+    x = wl.random_i8(rng, (N, Cin, H, W), 6)
+    w = wl.random_i8(rng, (Cout, Cin // g, kh, kw), 6)
+    lut = rng.integers(-1000, 1000, size=(64, 64)).astype(np.int32)
+    a = orc.approx_conv2d(lut, 6, x, w, (sh, sw), (ph, pw), (dh, dw), g, form="direct")
+    b = orc.approx_conv2d(lut, 6, x, w, (sh, sw), (ph, pw), (dh, dw), g, form="im2col")
+    assert (a == b).all()
+    if g == 1:   # the expanded matrix itself, multiplied with the linear-layer routine
+        col = orc.im2col(x, kh, kw, (sh, sw), (ph, pw), (dh, dw))
+        acc = orc.approx_linear(lut, 6, col, w.reshape(Cout, -1))
+        Ho, Wo = a.shape[2:]
+        assert (acc.reshape(N, Ho, Wo, Cout).transpose(0, 3, 1, 2) == a).all()
+
+
+CONVT_CASES = [
+    # N, Cin, H, W, Cout, k, stride, pad
+    (2, 3, 1, 1, 4, 4, 1, 0),
+    (1, 4, 4, 4, 3, 4, 2, 1),
+    (2, 2, 5, 3, 2, 3, 2, 0),
+    (1, 3, 3, 4, 2, 3, 1, 1),
+    (1, 2, 4, 4, 2, 5, 3, 2),
+]
+
+
+@pytest.mark.parametrize("case", CONVT_CASES)
+def test_exact_table_is_library_conv_transpose2d(case):
+    N, Cin, H, W, Cout, k, s, p = case
+    rng = np.random.default_rng(sum(case))
+    x = wl.random_i8(rng, (N, Cin, H, W), 8)
+    w = wl.random_i8(rng, (Cin, Cout, k, k), 8)
+    want = torch.nn.functional.conv_transpose2d(torch.from_numpy(x.astype(np.float64)),
+                                                torch.from_numpy(w.astype(np.float64)), stride=s, padding=p).numpy()
+    got = orc.approx_conv_transpose2d(wl.exact_lut(8), 8, x, w, s, p)
+    assert got.shape == want.shape
+    assert (got.astype(np.float64) == want).all()
+
+
+def test_linear_in_the_table():
+    rng = np.random.default_rng(7)
+    A = wl.random_i8(rng, (5, 40), 5)
+    W = wl.random_i8(rng, (6, 40), 5)
+    t1 = rng.integers(-500, 500, size=(32, 32)).astype(np.int32)
+    t2 = rng.integers(-500, 500, size=(32, 32)).astype(np.int32)
+    f = lambda t: orc.approx_linear(t, 5, A, W).astype(np.int64)
+    assert (f(t1 + t2) == f(t1) + f(t2)).all()
+    assert (f(3 * t1) == 3 * f(t1)).all()
+    x = wl.random_i8(rng, (1, 2, 5, 5), 5)
+    w = wl.random_i8(rng, (3, 2, 3, 3), 5)
+    g = lambda t: orc.approx_conv2d(t, 5, x, w, (1, 1), (1, 1)).astype(np.int64)
+    assert (g(t1 + t2) == g(t1) + g(t2)).all()
+    wt = wl.random_i8(rng, (2, 3, 3, 3), 5)
+    h = lambda t: orc.approx_conv_transpose2d(t, 5, x, wt, 2, 1).astype(np.int64)
+    assert (h(t1 + t2) == h(t1) + h(t2)).all()
+
+
+def test_projection_tables_fix_operand_order():
+    """T[a][w] = a gives row sums of A; T[a][w] = w gives row sums of W; a one-hot
+    table counts the joint occurrences of (a0, w0)."""
+    bits = 4
+    rng = np.random.default_rng(3)
+    A = wl.random_i8(rng, (6, 50), bits)
+    W = wl.random_i8(rng, (4, 50), bits)
+    v = np.arange(-8, 8, dtype=np.int32)
+    ta = np.repeat(v[:, None], 16, axis=1)       # entry = activation operand
+    tw = np.repeat(v[None, :], 16, axis=0)       # entry = weight operand
+    sa = A.astype(np.int64).sum(1)
+    sw = W.astype(np.int64).sum(1)
+    assert (orc.approx_linear(ta, bits, A, W) == np.repeat(sa[:, None], 4, 1)).all()
+    assert (orc.approx_linear(tw, bits, A, W) == np.repeat(sw[None, :], 6, 0)).all()
+    a0, w0 = -3, 5
+    one = np.zeros((16, 16), dtype=np.int32)
+    one[a0 + 8, w0 + 8] = 1
+    want = ((A[:, None, :] == a0) & (W[None, :, :] == w0)).sum(-1)
+    assert (orc.approx_linear(one, bits, A, W) == want).all()
+    # convolution: T = a gives the box sum of the input, identical for every output channel
+    x = wl.random_i8(rng, (1, 2, 6, 6), bits)
+    w = wl.random_i8(rng, (3, 2, 3, 3), bits)
+    box = torch.nn.functional.conv2d(torch.from_numpy(x.astype(np.float64)), torch.ones(1, 2, 3, 3, dtype=torch.float64),
+                                     padding=1).numpy()
+    got = orc.approx_conv2d(ta, bits, x, w, (1, 1), (1, 1))
+    assert (got == np.repeat(box, 3, 1)).all()
+    # conv-transpose with T = w: each output gets the sum of the filter taps that reach it
+    xt = wl.random_i8(rng, (1, 2, 3, 3), bits)
+    wt = wl.random_i8(rng, (2, 3, 4, 4), bits)
+    want = torch.nn.functional.conv_transpose2d(torch.ones(1, 2, 3, 3, dtype=torch.float64),
+                                                torch.from_numpy(wt.astype(np.float64)), stride=2, padding=1).numpy()
+    assert (orc.approx_conv_transpose2d(tw, bits, xt, wt, 2, 1) == want).all()
+
+
+def test_constant_table_conv_counts_every_tap_including_padding():
+    c = 11
+    t = np.full((16, 16), c, dtype=np.int32)
+    rng = np.random.default_rng(5)
+    x = wl.random_i8(rng, (2, 4, 5, 6), 4)
+    w = wl.random_i8(rng, (3, 4, 3, 3), 4)
+    got = orc.approx_conv2d(t, 4, x, w, (1, 1), (1, 1))
+    assert (got == c * 4 * 9).all()           # borders included
+    wg = wl.random_i8(rng, (4, 2, 3, 3), 4)
+    got = orc.approx_conv2d(t, 4, x, wg, (2, 1), (2, 0), (1, 2), 2)
+    assert (got == c * 2 * 9).all()
+
+
+def _valid_taps(o, k, s, p, size):
+    return sum(1 for kk in range(k) if (o + p - kk) >= 0 and (o + p - kk) % s == 0 and (o + p - kk) // s < size)
+
+
+@pytest.mark.parametrize("case", CONVT_CASES)
+def test_constant_table_conv_transpose_counts_real_pairs_only(case):
+    N, Cin, H, W, Cout, k, s, p = case
+    c = 3
+    t = np.full((16, 16), c, dtype=np.int32)
+    rng = np.random.default_rng(9)
+    x = wl.random_i8(rng, (N, Cin, H, W), 4)
+    w = wl.random_i8(rng, (Cin, Cout, k, k), 4)
+    got = orc.approx_conv_transpose2d(t, 4, x, w, s, p)
+    Ho, Wo = got.shape[2:]
+    cy = np.array([_valid_taps(o, k, s, p, H) for o in range(Ho)])
+    cx = np.array([_valid_taps(o, k, s, p, W) for o in range(Wo)])
+    want = c * Cin * cy[:, None] * cx[None, :]
+    assert (got == want[None, None]).all()
+
+
+@pytest.mark.parametrize("bits", [6, 7, 8])
+def test_generated_tables_symmetric_and_in_range(bits):
+    t = wl.make_lut(bits).astype(np.int64)
+    H = 1 << (bits - 1)
+    E = wl.LUT_ERR[bits]
+    assert (t == t.T).all()
+    v = np.arange(-H, H)
+    assert (np.abs(t - v[:, None] * v[None, :]) <= E).all()
+    assert np.abs(t).max() <= H * H + E
+    assert t.min() >= -32768 and t.max() <= 32767
+    assert (t[H] != 0).any()                  # the zero-operand row carries error too
+    rng = np.random.default_rng(bits)
+    A = wl.random_i8(rng, (5, 30), bits)
+    W = wl.random_i8(rng, (4, 30), bits)
+    lut = wl.make_lut(bits)
+    assert (orc.approx_linear(lut, bits, A, W).T == orc.approx_linear(lut, bits, W, A)).all()
+
+
+def test_accumulator_wraps_mod_2_32():
+    t = np.full((4, 4), 2**30, dtype=np.int32)
+    A = np.zeros((1, 5), dtype=np.int8)
+    W = np.zeros((1, 5), dtype=np.int8)
+    want = np.int32((5 * 2**30 + 2**31) % 2**32 - 2**31)      # 5 * 2^30 wraps to 2^30
+    assert orc.approx_linear(t, 2, A, W)[0, 0] == want
+
+
+def test_rejects_operands_outside_the_bit_range():
+    A = np.array([[4]], dtype=np.int8)
+    W = np.array([[0]], dtype=np.int8)
+    with pytest.raises(ValueError):
+        orc.approx_linear(wl.exact_lut(3), 3, A, W)
+
+
+# ---- quantiser / dequantiser closed forms (Sec. III-A) ---------------------------------
+
+def test_quantiser_round_half_even_and_clamp():
+    s = np.float32(0.5)
+    x = np.array([0.25, 0.75, 1.25, -0.25, -0.75, 1e9, -1e9, np.nan, 63.4, 63.6, -64.0], dtype=np.float32)
+    # x/s = 0.5, 1.5, 2.5, -0.5, -1.5 -> 0, 2, 2, -0, -2 ; clamp to +-127 ; NaN -> 0
+    assert orc.quantize(x, s, 8).tolist() == [0, 2, 2, 0, -2, 127, -127, 0, 127, 127, -127]
+    assert orc.quantize(x, s, 6).tolist() == [0, 2, 2, 0, -2, 31, -31, 0, 31, 31, -31]
+
+
+@pytest.mark.parametrize("bits", [4, 6, 7, 8])
+def test_quantiser_maxabs_scale_properties(bits):
+    rng = np.random.default_rng(bits)
+    x = rng.standard_normal(5000).astype(np.float32)
+    Q = (1 << (bits - 1)) - 1
+    amax = orc.absmax(x)
+    assert amax == np.abs(x).max()
+    s = orc.scale_from_amax(amax, bits)
+    assert s == np.float32(amax) / np.float32(Q)
+    q = orc.quantize(x, s, bits)
+    assert q.min() >= -Q and q.max() <= Q
+    assert abs(int(q[np.argmax(np.abs(x))])) == Q               # the extreme element maps to +-Q
+    err = np.abs(x.astype(np.float64) - float(s) * q.astype(np.float64))
+    assert err.max() <= float(s) * 0.5 * (1 + 1e-6)             # |x - s q| <= s/2 inside the range
+    assert (orc.quantize(-x, s, bits) == -q).all()              # symmetric range
+    assert (orc.quantize(np.array([1.5 * amax, -1.5 * amax], dtype=np.float32), s, bits) == [Q, -Q]).all()
+    assert orc.scale_from_amax(0.0, bits) == 1.0
+    assert orc.absmax(np.array([np.nan, -3.0, 2.0], dtype=np.float32)) == 3.0
+
+
+def test_dequant_two_rounded_steps():
+    acc = np.array([2**24 + 1, -(2**24 + 1), 3, -7], dtype=np.int32)
+    y = orc.dequant(acc, 1.0, 4, 1, 1)
+    assert y.tolist() == [16777216.0, -16777216.0, 3.0, -7.0]   # int -> fp32 rounds to nearest even
+    # layout (outer, channel, inner) and per-channel bias
+    acc = np.arange(12, dtype=np.int32).reshape(2, 3, 2)
+    bias = np.array([0.5, -1.0, 100.0], dtype=np.float32)
+    y = orc.dequant(acc, 0.25, 2, 3, 2, bias)
+    want = acc.astype(np.float32) * np.float32(0.25) + bias[None, :, None]
+    assert (y == want).all()
+    # product rounded before the bias is added (no fused multiply-add):
+    acc = np.array([3], dtype=np.int32)
+    s = np.float32(1.0) / np.float32(3.0)
+    b = np.array([-1.0], dtype=np.float32)
+    y = orc.dequant(acc, s, 1, 1, 1, b)
+    assert y[0] == np.float32(np.float32(3.0) * s) + b[0]
+
+
+def test_exact_8bit_layer_close_to_fp32_layer():
+    """An exact-product 8-bit layer reproduces the fp32 layer up to quantisation noise (Sec. V-A)."""
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((4, 8, 10, 10)).astype(np.float32)
+    w = (rng.standard_normal((6, 8, 3, 3)) * 0.1).astype(np.float32)
+    s_x = orc.scale_from_amax(orc.absmax(x), 8)
+    s_w = orc.scale_from_amax(orc.absmax(w), 8)
+    acc = orc.approx_conv2d(wl.exact_lut(8), 8, orc.quantize(x, s_x, 8), orc.quantize(w, s_w, 8), (1, 1), (1, 1))
+    y = orc.dequant(acc, np.float32(s_x) * np.float32(s_w), 4, 6, 100)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(x), torch.from_numpy(w), padding=1).numpy()
+    rel = np.linalg.norm(y - ref) / np.linalg.norm(ref)
+    assert rel < 0.03, rel
+
+
+# ---- fp32 glue ---------------------------------------------------------------------------
+
+def test_exp_sigmoid_tanh_against_libm():
+    xs = np.concatenate([np.linspace(-30, 30, 20001), np.linspace(-1, 1, 2001)]).astype(np.float32)
+    e = orc.exp(xs).astype(np.float64)
+    ref = np.exp(xs.astype(np.float64))
+    assert np.max(np.abs(e - ref) / ref) < 4 * 2.0**-23
+    sg = orc.sigmoid(xs).astype(np.float64)
+    assert np.max(np.abs(sg - 1 / (1 + np.exp(-xs.astype(np.float64))))) < 1e-6
+    th = orc.tanh(xs).astype(np.float64)
+    assert np.max(np.abs(th - np.tanh(xs.astype(np.float64)))) < 1e-6
+    assert orc.sigmoid(np.zeros(1, np.float32))[0] == 0.5
+    assert orc.tanh(np.zeros(1, np.float32))[0] == 0.0
+    assert (orc.tanh(-xs) == -orc.tanh(xs)).all()
+    assert orc.exp(np.array([-1000.0, 1000.0], np.float32)).tolist() == orc.exp(np.array([-87.0, 88.0], np.float32)).tolist()
+    assert math.isfinite(orc.exp(np.array([1000.0], np.float32))[0])
+
+
+def test_small_glue_ops():
+    x = np.array([-1.0, 0.0, 2.5, -0.0, np.nan], dtype=np.float32)
+    assert orc.relu(x).tolist() == [0.0, 0.0, 2.5, 0.0, 0.0]
+    a = np.array([1e8, 1.0], dtype=np.float32)
+    b = np.array([1.0, 2.0], dtype=np.float32)
+    assert (orc.add(a, b) == a + b).all()
+    rng = np.random.default_rng(2)
+    t = rng.standard_normal((2, 3, 4, 4)).astype(np.float32)
+    got = orc.avgpool_hw(t)
+    want = np.empty((2, 3), np.float32)
+    for i in range(2):
+        for j in range(3):
+            s = np.float32(0)
+            for v in t[i, j].reshape(-1):
+                s = np.float32(s + v)
+            want[i, j] = s * (np.float32(1) / np.float32(16))
+    assert (got == want).all()
+    sc = orc.shortcut_a(t, 6)                  # 3 -> 6 channels: (6-3)//2 = 1 zero plane in front, 2 behind
+    assert sc.shape == (2, 6, 2, 2)
+    assert (sc[:, 1:4] == t[:, :, ::2, ::2]).all() and (sc[:, 0] == 0).all() and (sc[:, 4:] == 0).all()
+
+
+def test_lstm_cell_matches_library_lstm_with_exact_table():
+    """Exact-product 8-bit LSTM tracks torch.nn.LSTM (gate order i, f, g, o) to quantisation noise."""
+    from oracle import networks
+    rng = np.random.default_rng(4)
+    T, B, I, Hs = 6, 3, 16, 8
+    cfg = dict(bits=8, lut=wl.exact_lut(8),
+               x=rng.standard_normal((T, B, I)).astype(np.float32),
+               w_ih=(rng.standard_normal((4 * Hs, I)) * 0.3).astype(np.float32),
+               w_hh=(rng.standard_normal((4 * Hs, Hs)) * 0.3).astype(np.float32),
+               bias=(rng.standard_normal(4 * Hs) * 0.1).astype(np.float32))
+    out = networks.lstm(cfg)
+    m = torch.nn.LSTM(I, Hs)
+    with torch.no_grad():
+        m.weight_ih_l0.copy_(torch.from_numpy(cfg["w_ih"]))
+        m.weight_hh_l0.copy_(torch.from_numpy(cfg["w_hh"]))
+        m.bias_ih_l0.copy_(torch.from_numpy(cfg["bias"]))
+        m.bias_hh_l0.zero_()
+        ref, (hn, cn) = m(torch.from_numpy(cfg["x"]))
+    assert np.abs(out["hs"] - ref.numpy()).max() < 0.03
+    assert np.abs(out["c"] - cn[0].numpy()).max() < 0.05
+
+
+def test_network_runners_track_fp32_networks_with_exact_table():
+    """ResNet-style and generator-style runners with the exact 8-bit table stay close to the
+    same networks evaluated in fp32 by library convolutions (loose: quantisation noise only)."""
+    from oracle import networks
+    F = torch.nn.functional
+    cfg = wl.config3(batch=2)
+    cfg["lut"] = wl.exact_lut(8)
+    out = networks.resnet20(cfg)
+    plan = wl.resnet20_plan()
+    ws = [torch.from_numpy(w) for w in cfg["convs"]]
+    x = torch.relu(F.conv2d(torch.from_numpy(cfg["x"]), ws[0], padding=1))
+    i = 1
+    while i < len(plan):
+        cin, cout, s = plan[i]
+        y = torch.relu(F.conv2d(x, ws[i], stride=s, padding=1))
+        z = F.conv2d(y, ws[i + 1], padding=1)
+        if s == 1 and cin == cout:
+            sc = x
+        else:
+            sc = F.pad(x[:, :, ::2, ::2], (0, 0, 0, 0, (cout - cin) // 2, (cout - cin) // 2))
+        x = torch.relu(z + sc)
+        i += 2
+    logits = x.mean((2, 3)) @ torch.from_numpy(cfg["fc_w"]).T
+    ref = logits.numpy()
+    assert np.linalg.norm(out["logits"] - ref) / np.linalg.norm(ref) < 0.08
+    assert len(out["scales"]) == 20
+    # frozen scales reproduce the calibrated run bit for bit
+    again = networks.resnet20(cfg, scales=out["scales"])
+    assert (again["logits"] == out["logits"]).all()
+
+    g = wl.config5(bits=8, batch=2)
+    g["lut"] = wl.exact_lut(8)
+    og = networks.dcgan(g)
+    x = torch.from_numpy(g["z"])
+    for j, ((cin, cout, s, p), w) in enumerate(zip(g["plan"], g["ws"])):
+        x = F.conv_transpose2d(x, torch.from_numpy(w), stride=s, padding=p)
+        x = torch.tanh(x) if j == 4 else torch.relu(x)
+    ref = x.numpy()
+    assert og["out"].shape == (2, 3, 64, 64)
+    assert np.linalg.norm(og["out"] - ref) / np.linalg.norm(ref) < 0.08
