@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the table-lookup hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch that is already resident in HBM:
+quantise the fp32 input -> approximate layer(s) -> dequantise (+ the fp32 glue of the network
+configurations).  Default workload: the 3x3 convolution layer the metric is quoted on
+(batch 32, 64 -> 64 channels, 32x32, 8-bit table).  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1|2|3|4|5] [--bits B] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+LDS_LANES_PER_CLK_PER_CU = 32      # 32 banks x 4 B: one 16-bit gather lane per bank per clock
+MODEL_CLOCK_GHZ = 2.4
+MODEL_CUS = 256
+
+
+def _f(x):
+    return np.float32(x)
+
+
+def build_step(cfg_id, bits, torch, B, gnet, wl):
+    """Returns (step_fn, core_fn, macs, workload_name, dtype) for a configuration.
+    step_fn(): one pass of the whole path; core_fn(): only the dominant table-lookup call."""
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    if cfg_id == 1:
+        c = wl.config1()
+        L = B.Lut(c["lut"], 8)
+        A, W = dev(c["A"]), dev(c["W"])
+        acc = torch.empty((64, 128), dtype=torch.int32, device="cuda")
+        y = torch.empty((64, 128), dtype=torch.float32, device="cuda")
+
+        def core():
+            B.adapt_approx_linear(L, A, W, out=acc)
+
+        def step():
+            core()
+            B.adapt_dequant_i32(acc, c["scale"], 64, 128, 1, out=y)
+        return step, core, 64 * 256 * 128, "config1: approx_linear 64x256x128, 8-bit table", L
+    if cfg_id == 2:
+        c = wl.config2()
+        L = B.Lut(c["lut"], 8)
+        x, w = dev(c["x"]), dev(c["w"])
+        s_x = gnet.calibrated_scale(x, 8)
+        qw, s_w = gnet.quantize_weights(w, 8)
+        qx = torch.empty(x.shape, dtype=torch.int8, device="cuda")
+        acc = torch.empty((32, 64, 32, 32), dtype=torch.int32, device="cuda")
+        y = torch.empty((32, 64, 32, 32), dtype=torch.float32, device="cuda")
+        s_out = _f(s_x) * _f(s_w)
+        B.adapt_quantize_f32(x, s_x, 8, out=qx)
+
+        def core():
+            B.adapt_approx_conv2d(L, qx, qw, (1, 1), (1, 1), out=acc)
+
+        def step():
+            B.adapt_quantize_f32(x, s_x, 8, out=qx)
+            core()
+            B.adapt_dequant_i32(acc, s_out, 32, 64, 1024, out=y)
+        return step, core, wl.lut_macs_conv2d(32, 64, 32, 32, 64, 3, 3, 1, 1, 1, 1), \
+            "config2: approx_conv2d 3x3 s1 p1, batch 32, 64->64 ch, 32x32, 8-bit table", L
+    if cfg_id == 3:
+        c = wl.config3()
+        net = gnet.ResNet20(c)
+        x = dev(c["x"])
+        net.forward(x)            # calibration pass (host reads), scales frozen afterwards
+
+        def step():
+            net.forward(x)
+        return step, None, gnet.lut_macs_resnet20(128), "config3: ResNet-20-style CNN, batch 128, 8-bit table", net
+    if cfg_id == 4:
+        c = wl.config4()
+        net = gnet.LSTM(c)
+        x = dev(c["x"])
+        net.forward(x)
+
+        def step():
+            net.forward(x)
+        return step, None, gnet.lut_macs_lstm(100, 64, 512, 512), "config4: LSTM 512/512, seq 100, batch 64, 7-bit table", net
+    if cfg_id == 5:
+        c = wl.config5(bits=bits)
+        net = gnet.DCGAN(c)
+        z = dev(c["z"])
+        net.forward(z)
+
+        def step():
+            net.forward(z)
+        return step, None, gnet.lut_macs_dcgan(256, c["plan"]), f"config5: DCGAN-style generator, batch 256, {bits}-bit table", net
+    raise SystemExit(f"unknown config {cfg_id}")
+
+
+def cpu_baseline(cfg_id, bits, wl):
+    """The parity oracle as it stands, timed on this host's cores, on a bounded sample."""
+    import oracle as orc
+    from oracle import networks as onet
+    th = orc.host_threads()
+    if cfg_id == 1:
+        c = wl.config1()
+        reps, macs = 20, 64 * 256 * 128
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            acc = orc.approx_linear(c["lut"], 8, c["A"], c["W"], threads=th)
+            orc.dequant(acc, c["scale"], 64, 128, 1)
+        dt = (time.perf_counter() - t0) / reps
+        return dict(value=macs / dt, unit="LUT-MAC/s", cores=th, kind="oracle", sample=f"full config-1 layer, mean of {reps} passes")
+    if cfg_id == 2:
+        c = wl.config2()
+        s_x = orc.scale_from_amax(orc.absmax(c["x"]), 8)
+        s_w = orc.scale_from_amax(orc.absmax(c["w"]), 8)
+        qw = orc.quantize(c["w"], s_w, 8)
+        macs = wl.lut_macs_conv2d(32, 64, 32, 32, 64, 3, 3, 1, 1, 1, 1)
+        best = 1e30
+        reps = 5
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            qx = orc.quantize(c["x"], s_x, 8)
+            acc = orc.approx_conv2d(c["lut"], 8, qx, qw, (1, 1), (1, 1), threads=th)
+            orc.dequant(acc, _f(s_x) * _f(s_w), 32, 64, 1024)
+            best = min(best, time.perf_counter() - t0)
+        return dict(value=macs / best, unit="LUT-MAC/s", cores=th, kind="oracle",
+                    sample=f"full config-2 step (32 images: quantise + conv + dequantise), best of {reps} passes")
+    if cfg_id == 3:
+        c = wl.config3(batch=32)
+        t0 = time.perf_counter()
+        onet.resnet20(c, threads=th)
+        dt = time.perf_counter() - t0
+        macs = 40551040 * 32
+        return dict(value=macs / dt, unit="LUT-MAC/s", cores=th, kind="oracle", sample="32 of 128 images, one pass incl. calibration")
+    if cfg_id == 4:
+        c = wl.config4()
+        t0 = time.perf_counter()
+        onet.lstm(c, threads=th, steps=10)
+        dt = time.perf_counter() - t0
+        return dict(value=134217728 * 10 / dt, unit="LUT-MAC/s", cores=th, kind="oracle", sample="first 10 of 100 time steps")
+    c = wl.config5(bits=bits, batch=32)
+    t0 = time.perf_counter()
+    onet.dcgan(c, threads=th)
+    dt = time.perf_counter() - t0
+    return dict(value=104628224 * 32 / dt, unit="LUT-MAC/s", cores=th, kind="oracle", sample="32 of 256 latent vectors, one pass incl. calibration")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--bits", type=int, default=8, help="table bits for config 5 (6 or 8)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc (reported as roofline.traffic)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on one GPU only (pure batch sharding needs no exchange step; "
+                         "see DESIGN.md). Run with --gpus 1.")
+
+    import torch
+    from paper_2203_04071_amd import binding as B, networks as gnet, workloads as wl
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    B.load()
+    torch.cuda.set_device(0)
+    step, core, macs, name, _keep = build_step(args.config, args.bits, torch, B, gnet, wl)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+
+    # dominant kernel: HIP events on the launch stream around the table-lookup call
+    roof = None
+    cus = B.adapt_device_cu_count()
+    peak = cus * LDS_LANES_PER_CLK_PER_CU * MODEL_CLOCK_GHZ * 1e9
+    if core is not None:
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        for a, b in evs:
+            a.record()
+            core()
+            b.record()
+        torch.cuda.synchronize()
+        kms = np.array([a.elapsed_time(b) for a, b in evs])
+        k_avg = float(kms.mean())
+        achieved = macs / (k_avg * 1e-3)
+        roof = dict(bound="lds", achieved=achieved / 1e12, peak=peak / 1e12, unit="Tlookup/s", frac=achieved / peak,
+                    traffic=args.traffic_bytes, kernel_ms_avg=k_avg, kernel_ms_min=float(kms.min()),
+                    peak_model=f"{cus} CUs x {LDS_LANES_PER_CLK_PER_CU} LDS bank-lanes/clk x {MODEL_CLOCK_GHZ} GHz; "
+                               "1 lookup (2 B) per LUT-MAC")
+    else:
+        achieved = macs / (ms_per_step * 1e-3)
+        roof = dict(bound="lds", achieved=achieved / 1e12, peak=peak / 1e12, unit="Tlookup/s", frac=achieved / peak,
+                    traffic=args.traffic_bytes, note="whole network step (all kernels) against the LDS lookup peak")
+
+    out = {
+        "metric": "approximate MACs/sec (LUT-MAC/s), whole step: quantise + table-lookup layer(s) + dequantise",
+        "value": macs / (ms_per_step * 1e-3),
+        "unit": "LUT-MAC/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8 operands, int16 table, int32 accumulate, fp32 scale",
+        "data": "synthetic (seeded)",
+        "config": {"workload": name, "lut_macs_per_step": macs},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config, args.bits, wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,147 @@
+/*
+ * adapt_mi355 -- approximate-multiplier GEMM / convolution by table lookup on MI355X (gfx950).
+ *
+ * C ABI of the hot path of AdaPT (arXiv 2203.04071): per layer
+ *     quantise (Sec. III-A)  ->  matrix product in which every b-bit x b-bit
+ *     multiply is one entry of a 2^b x 2^b table (Sec. III-C, IV)  ->  dequantise,
+ * for linear layers, 2-D convolutions (Sec. III-B) and transposed convolutions
+ * (the generator networks of Sec. V), plus the small fp32 operations that sit
+ * between approximate layers in the CNN / LSTM / GAN workloads.
+ *
+ * General rules
+ *   - Every function returns ADAPT_OK (0) or a negative error code; nothing
+ *     throws, aborts or synchronises the device unless stated.  A text for the
+ *     last error of the calling thread is available from adapt_last_error().
+ *   - Pointers named *_dev are DEVICE pointers owned by the caller; pointers
+ *     named *_host are HOST pointers.  The library never frees caller memory
+ *     and never keeps a caller pointer after the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Kernels are enqueued on it and the call returns without waiting.
+ *   - Tensors are dense, row-major, in the layouts stated per function.
+ *   - b = bits, H = 2^(b-1), Q = H - 1.  Quantised operands are signed integers
+ *     in [-H, H-1] stored one per int8.  Passing values outside that range for
+ *     the table's bit width is a caller error (the kernels wrap them into range,
+ *     they never read outside the table).
+ *   - Accumulators are int32 with two's-complement wrap-around.
+ *   - Output buffers are overwritten, never accumulated into.
+ *   - Handles (adapt_lut) own their device memory and belong to the device that
+ *     was current when they were created.
+ *   - Two calls that overlap in time on different streams are safe; workspaces
+ *     are allocated per call in stream order.
+ */
+#ifndef ADAPT_MI355_H
+#define ADAPT_MI355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ADAPT_OK 0
+#define ADAPT_ERR_INVALID_ARGUMENT (-1) /* null pointer, bits outside [2,8], non-positive dims, bad geometry */
+#define ADAPT_ERR_UNSUPPORTED (-2)      /* valid request this build does not implement (e.g. groups > 1) */
+#define ADAPT_ERR_LUT_RANGE (-3)        /* reserved: table entry not representable */
+#define ADAPT_ERR_HIP (-4)              /* a HIP runtime call or kernel launch failed */
+#define ADAPT_ERR_OUT_OF_MEMORY (-5)
+
+/* thread-local text of the most recent error on this thread ("" if none); static storage */
+const char *adapt_last_error(void);
+
+/* Number of compute units of the current device (used by callers to report rooflines). <0 on error. */
+int adapt_device_cu_count(void);
+
+/* ------------------------------------------------------------------------------------------------
+ * Multiplier table (Sec. III-C: one look-up table per approximate compute unit, a 1:1 image of the
+ * multiplier; Sec. III: the unit may differ from layer to layer, so it is a per-call argument).
+ *
+ * table_host: HOST int32 [2^b][2^b]; the product of activation a and weight w, both in [-H, H-1],
+ * is table_host[(a + H) * 2^b + (w + H)].  The table may be arbitrary (not symmetric, not zero for a
+ * zero operand).  The call copies it (synchronously) into a device image in the library's private
+ * order; the host array may be freed afterwards.
+ * storage chosen: 0 = one int16 table (all entries in [-32768, 32767]);
+ *                 1 = two 16-bit tables (high and low halves of int32 entries; kernels run twice).
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct adapt_lut adapt_lut;
+
+int adapt_lut_create(adapt_lut **out, int bits, const int32_t *table_host);
+int adapt_lut_destroy(adapt_lut *lut);
+int adapt_lut_info(const adapt_lut *lut, int *bits, int *storage, int32_t *min_entry, int32_t *max_entry);
+
+/* ------------------------------------------------------------------------------------------------
+ * Quantiser (Sec. III-A: affine map real = scale * q, zero point 0, any bit width).
+ * ---------------------------------------------------------------------------------------------- */
+
+/* amax_dev[0] = max |x_i| over n fp32 values (NaNs skipped; 0 for n == 0).  This is the "max absolute
+ * number" scale choice of Sec. III-A; scale = amax / Q. */
+int adapt_absmax_f32(const float *x_dev, size_t n, float *amax_dev, void *stream);
+
+/* q_i = clamp(round_half_even(x_i / scale), -Q, Q), NaN -> 0.  scale > 0. */
+int adapt_quantize_f32(const float *x_dev, int8_t *q_dev, size_t n, float scale, int bits, void *stream);
+
+/* Dequantiser: y = float(acc) * scale, then (if bias_dev) + bias[c]; two separately rounded fp32
+ * operations (Sec. III-A real = A * q; Sec. III-B "+ b").  Element (o, c, i) sits at
+ * ((o * channels) + c) * inner + i:  linear -> outer = M, channels = N, inner = 1;
+ * convolution NCHW -> outer = N, channels = Cout, inner = Hout * Wout.  scale = s_x * s_w, formed in
+ * fp32 by the caller.  bias_dev: [channels] or NULL. */
+int adapt_dequant_i32(const int32_t *acc_dev, float *y_dev, size_t outer, size_t channels, size_t inner,
+                      float scale, const float *bias_dev, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Approximate layers (Sec. III-B, IV): every inner-product term is one table entry.
+ * ---------------------------------------------------------------------------------------------- */
+
+/* Linear layer y = x A^T:  acc[m][n] = sum_k T[a[m][k]][w[n][k]].
+ * a_dev [M][K], w_dev [N][K], acc_dev [M][N].  M, N >= 0 (empty is a no-op), K >= 0 (K == 0 writes zeros). */
+int adapt_approx_linear(const adapt_lut *lut, const int8_t *a_dev, const int8_t *w_dev, int32_t *acc_dev,
+                        int M, int K, int N, void *stream);
+
+/* 2-D convolution, x NCHW [N][Cin][H][W], w [Cout][Cin/groups][kh][kw], acc [N][Cout][Hout][Wout],
+ * Hout = (H + 2 pad_h - dil_h (kh-1) - 1) / stride_h + 1 (likewise Wout).  The layer is the product of
+ * the expanded input matrix with the filter matrix (Sec. III-B); a tap that falls into the padding is
+ * an entry of that matrix equal to quantised zero, so T[0][w] IS added for it.
+ * groups must be 1 in this build (else ADAPT_ERR_UNSUPPORTED). */
+int adapt_approx_conv2d(const adapt_lut *lut, const int8_t *x_dev, const int8_t *w_dev, int32_t *acc_dev,
+                        int N, int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w,
+                        int pad_h, int pad_w, int dil_h, int dil_w, int groups, void *stream);
+
+/* Transposed 2-D convolution (generator networks), x [N][Cin][H][W], w [Cin][Cout][kh][kw],
+ * acc [N][Cout][Hout][Wout], Hout = (H-1) stride - 2 pad + kh; input pixel (iy, ix) meets tap (ky, kx)
+ * at output (iy stride - pad + ky, ix stride - pad + kx).  Only real (input, weight) pairs are looked
+ * up; the zeros implied between input pixels never enter the multiplier.  output_padding 0, dilation 1. */
+int adapt_approx_conv_transpose2d(const adapt_lut *lut, const int8_t *x_dev, const int8_t *w_dev,
+                                  int32_t *acc_dev, int N, int Cin, int H, int W, int Cout, int kh, int kw,
+                                  int stride, int pad, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * fp32 operations between approximate layers.  Each element is produced by single IEEE fp32
+ * operations in the stated order (no fused multiply-add unless stated), so that the integers the next
+ * quantiser produces are reproducible.  In-place use (y_dev == x_dev) is allowed.
+ * ---------------------------------------------------------------------------------------------- */
+
+/* y = x > 0 ? x : 0 */
+int adapt_relu_f32(const float *x_dev, float *y_dev, size_t n, void *stream);
+/* y = a + b, optionally followed by the ReLU above (relu != 0): residual connection */
+int adapt_add_f32(const float *a_dev, const float *b_dev, float *y_dev, size_t n, int relu, void *stream);
+/* y[i] = (sequential row-major fp32 sum of x[i][0..HW-1]) * (1.0f / HW): global average pool */
+int adapt_avgpool_hw_f32(const float *x_dev, float *y_dev, size_t NC, size_t HW, void *stream);
+/* parameter-free residual shortcut: y[n][c][oy][ox] = x[n][c - (Cout-Cin)/2][2 oy][2 ox] or 0 outside;
+ * y is [N][Cout][(H+1)/2][(W+1)/2] */
+int adapt_shortcut_a_f32(const float *x_dev, float *y_dev, int N, int Cin, int H, int W, int Cout, void *stream);
+/* y = tanh(x) computed as sign(x) (1 - e) / (1 + e), e = exp(-2|x|), with the library's written-out
+ * exp (range reduction by ln 2 in two fused steps, degree-7 Horner polynomial with fused multiply-adds) */
+int adapt_tanh_f32(const float *x_dev, float *y_dev, size_t n, void *stream);
+/* y = 1 / (1 + exp(-x)) with the same exp */
+int adapt_sigmoid_f32(const float *x_dev, float *y_dev, size_t n, void *stream);
+/* LSTM memory cell (Sec. III-B "RNN Layer"), gate order i, f, g, o along the 4*Hs axis:
+ *   pre = (float(acc_ih) * s_ih + float(acc_hh) * s_hh) + bias   (bias_dev NULL = 0)
+ *   c = f * c + i * g  (two products, then one sum);  h = o * tanh(c)
+ * acc_ih_dev, acc_hh_dev [B][4 Hs] int32; c_dev [B][Hs] updated in place; h_dev [B][Hs] written. */
+int adapt_lstm_cell_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh,
+                        const float *bias_dev, float *c_dev, float *h_dev, int B, int Hs, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADAPT_MI355_H */

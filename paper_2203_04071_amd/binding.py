@@ -1,0 +1,257 @@
+"""ctypes binding of libadapt_mi355.so: same names as the C ABI (include/adapt_mi355.h),
+argument marshalling only.  Tensors are torch CUDA tensors (PyTorch is used for device memory
+and streams, nothing else); every step of the path runs in the library's HIP kernels.
+
+There is no CPU fallback: if the library is not built, or no GPU is present, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch  # imported before the library so that one HIP runtime is shared by both
+
+from . import build as _build
+
+_lib = None
+
+ADAPT_OK = 0
+ERRORS = {-1: "INVALID_ARGUMENT", -2: "UNSUPPORTED", -3: "LUT_RANGE", -4: "HIP", -5: "OUT_OF_MEMORY"}
+
+EXPORTS = [
+    "adapt_last_error", "adapt_device_cu_count",
+    "adapt_lut_create", "adapt_lut_destroy", "adapt_lut_info",
+    "adapt_absmax_f32", "adapt_quantize_f32", "adapt_dequant_i32",
+    "adapt_approx_linear", "adapt_approx_conv2d", "adapt_approx_conv_transpose2d",
+    "adapt_relu_f32", "adapt_add_f32", "adapt_avgpool_hw_f32", "adapt_shortcut_a_f32",
+    "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32",
+]
+
+
+class AdaptError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"adapt_mi355 error {code} ({ERRORS.get(code, '?')}): {text}")
+        self.code = code
+
+
+def lib_path() -> str:
+    return _build.LIB
+
+
+def load() -> ctypes.CDLL:
+    """Load the built library (build it first only if nothing is built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build(force=True)
+    L = ctypes.CDLL(_build.LIB)
+    vp, i32, sz, f32 = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_float
+    L.adapt_last_error.restype = ctypes.c_char_p
+    L.adapt_last_error.argtypes = []
+    L.adapt_device_cu_count.argtypes = []
+    L.adapt_lut_create.argtypes = [ctypes.POINTER(vp), i32, vp]
+    L.adapt_lut_destroy.argtypes = [vp]
+    L.adapt_lut_info.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_int32),
+                                 ctypes.POINTER(ctypes.c_int32)]
+    L.adapt_absmax_f32.argtypes = [vp, sz, vp, vp]
+    L.adapt_quantize_f32.argtypes = [vp, vp, sz, f32, i32, vp]
+    L.adapt_dequant_i32.argtypes = [vp, vp, sz, sz, sz, f32, vp, vp]
+    L.adapt_approx_linear.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
+    L.adapt_approx_conv2d.argtypes = [vp, vp, vp, vp] + [i32] * 14 + [vp]
+    L.adapt_approx_conv_transpose2d.argtypes = [vp, vp, vp, vp] + [i32] * 9 + [vp]
+    L.adapt_relu_f32.argtypes = [vp, vp, sz, vp]
+    L.adapt_add_f32.argtypes = [vp, vp, vp, sz, i32, vp]
+    L.adapt_avgpool_hw_f32.argtypes = [vp, vp, sz, sz, vp]
+    L.adapt_shortcut_a_f32.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
+    L.adapt_tanh_f32.argtypes = [vp, vp, sz, vp]
+    L.adapt_sigmoid_f32.argtypes = [vp, vp, sz, vp]
+    L.adapt_lstm_cell_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, i32, i32, vp]
+    for name in EXPORTS:
+        if name != "adapt_last_error":
+            getattr(L, name).restype = i32
+    _lib = L
+    return L
+
+
+def _chk(rc):
+    if rc != ADAPT_OK:
+        raise AdaptError(rc, load().adapt_last_error().decode())
+
+
+def _stream(stream=None):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise TypeError("expected a contiguous CUDA tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected dtype {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+class Lut:
+    """Owner of an adapt_lut handle (multiplier table, Sec. III-C)."""
+
+    def __init__(self, table, bits: int):
+        t = np.ascontiguousarray(np.asarray(table, dtype=np.int32))
+        if t.size != (1 << bits) ** 2:
+            raise ValueError("table must have 2^bits x 2^bits entries")
+        self.bits = bits
+        self._h = ctypes.c_void_p()
+        _chk(load().adapt_lut_create(ctypes.byref(self._h), bits, t.ctypes.data_as(ctypes.c_void_p)))
+
+    @property
+    def handle(self):
+        return self._h
+
+    def info(self):
+        b, s = ctypes.c_int(), ctypes.c_int()
+        lo, hi = ctypes.c_int32(), ctypes.c_int32()
+        _chk(load().adapt_lut_info(self._h, ctypes.byref(b), ctypes.byref(s), ctypes.byref(lo), ctypes.byref(hi)))
+        return dict(bits=b.value, storage=s.value, min=lo.value, max=hi.value)
+
+    def close(self):
+        if self._h:
+            load().adapt_lut_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def adapt_device_cu_count() -> int:
+    n = load().adapt_device_cu_count()
+    if n < 0:
+        _chk(n)
+    return n
+
+
+def adapt_absmax_f32(x, amax_out=None, stream=None):
+    """Returns the 1-element device tensor holding max|x| (no synchronisation)."""
+    if amax_out is None:
+        amax_out = torch.empty(1, dtype=torch.float32, device=x.device)
+    _chk(load().adapt_absmax_f32(_ptr(x, torch.float32), x.numel(), _ptr(amax_out, torch.float32), _stream(stream)))
+    return amax_out
+
+
+def adapt_quantize_f32(x, scale: float, bits: int, out=None, stream=None):
+    if out is None:
+        out = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    _chk(load().adapt_quantize_f32(_ptr(x, torch.float32), _ptr(out, torch.int8), x.numel(), float(scale), bits,
+                                   _stream(stream)))
+    return out
+
+
+def adapt_dequant_i32(acc, scale: float, outer: int, channels: int, inner: int, bias=None, out=None, stream=None):
+    if out is None:
+        out = torch.empty(acc.shape, dtype=torch.float32, device=acc.device)
+    assert acc.numel() == outer * channels * inner
+    _chk(load().adapt_dequant_i32(_ptr(acc, torch.int32), _ptr(out, torch.float32), outer, channels, inner,
+                                  float(scale), _ptr(bias, torch.float32), _stream(stream)))
+    return out
+
+
+def adapt_approx_linear(lut: Lut, a, w, out=None, stream=None):
+    M, K = a.shape
+    N, K2 = w.shape
+    assert K == K2
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=a.device)
+    _chk(load().adapt_approx_linear(lut.handle, _ptr(a, torch.int8), _ptr(w, torch.int8), _ptr(out, torch.int32),
+                                    M, K, N, _stream(stream)))
+    return out
+
+
+def conv_out_hw(H, W, kh, kw, sh, sw, ph, pw, dh=1, dw=1):
+    return ((H + 2 * ph - dh * (kh - 1) - 1) // sh + 1, (W + 2 * pw - dw * (kw - 1) - 1) // sw + 1)
+
+
+def adapt_approx_conv2d(lut: Lut, x, w, stride=(1, 1), pad=(0, 0), dil=(1, 1), groups=1, out=None, stream=None):
+    N, Cin, H, W = x.shape
+    Cout, cg, kh, kw = w.shape
+    if out is None:
+        Ho, Wo = conv_out_hw(H, W, kh, kw, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1])
+        out = torch.empty((N, Cout, Ho, Wo), dtype=torch.int32, device=x.device)
+    _chk(load().adapt_approx_conv2d(lut.handle, _ptr(x, torch.int8), _ptr(w, torch.int8), _ptr(out, torch.int32),
+                                    N, Cin, H, W, Cout, kh, kw, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1],
+                                    groups, _stream(stream)))
+    return out
+
+
+def adapt_approx_conv_transpose2d(lut: Lut, x, w, stride=1, pad=0, out=None, stream=None):
+    N, Cin, H, W = x.shape
+    Cin2, Cout, kh, kw = w.shape
+    assert Cin == Cin2
+    if out is None:
+        Ho, Wo = (H - 1) * stride - 2 * pad + kh, (W - 1) * stride - 2 * pad + kw
+        out = torch.empty((N, Cout, Ho, Wo), dtype=torch.int32, device=x.device)
+    _chk(load().adapt_approx_conv_transpose2d(lut.handle, _ptr(x, torch.int8), _ptr(w, torch.int8),
+                                              _ptr(out, torch.int32), N, Cin, H, W, Cout, kh, kw, stride, pad,
+                                              _stream(stream)))
+    return out
+
+
+def adapt_relu_f32(x, out=None, stream=None):
+    if out is None:
+        out = torch.empty_like(x)
+    _chk(load().adapt_relu_f32(_ptr(x, torch.float32), _ptr(out, torch.float32), x.numel(), _stream(stream)))
+    return out
+
+
+def adapt_add_f32(a, b, relu=False, out=None, stream=None):
+    assert a.shape == b.shape
+    if out is None:
+        out = torch.empty_like(a)
+    _chk(load().adapt_add_f32(_ptr(a, torch.float32), _ptr(b, torch.float32), _ptr(out, torch.float32), a.numel(),
+                              1 if relu else 0, _stream(stream)))
+    return out
+
+
+def adapt_avgpool_hw_f32(x, out=None, stream=None):
+    N, C, H, W = x.shape
+    if out is None:
+        out = torch.empty((N, C), dtype=torch.float32, device=x.device)
+    _chk(load().adapt_avgpool_hw_f32(_ptr(x, torch.float32), _ptr(out, torch.float32), N * C, H * W, _stream(stream)))
+    return out
+
+
+def adapt_shortcut_a_f32(x, cout: int, out=None, stream=None):
+    N, C, H, W = x.shape
+    if out is None:
+        out = torch.empty((N, cout, (H + 1) // 2, (W + 1) // 2), dtype=torch.float32, device=x.device)
+    _chk(load().adapt_shortcut_a_f32(_ptr(x, torch.float32), _ptr(out, torch.float32), N, C, H, W, cout,
+                                     _stream(stream)))
+    return out
+
+
+def adapt_tanh_f32(x, out=None, stream=None):
+    if out is None:
+        out = torch.empty_like(x)
+    _chk(load().adapt_tanh_f32(_ptr(x, torch.float32), _ptr(out, torch.float32), x.numel(), _stream(stream)))
+    return out
+
+
+def adapt_sigmoid_f32(x, out=None, stream=None):
+    if out is None:
+        out = torch.empty_like(x)
+    _chk(load().adapt_sigmoid_f32(_ptr(x, torch.float32), _ptr(out, torch.float32), x.numel(), _stream(stream)))
+    return out
+
+
+def adapt_lstm_cell_f32(acc_ih, acc_hh, s_ih: float, s_hh: float, bias, c, h, stream=None):
+    B, H4 = acc_ih.shape
+    Hs = H4 // 4
+    _chk(load().adapt_lstm_cell_f32(_ptr(acc_ih, torch.int32), _ptr(acc_hh, torch.int32), float(s_ih), float(s_hh),
+                                    _ptr(bias, torch.float32), _ptr(c, torch.float32), _ptr(h, torch.float32), B, Hs,
+                                    _stream(stream)))
+    return h, c

@@ -1,0 +1,394 @@
+// C ABI of the library: argument checks, table handles, launch geometry.  All arithmetic of the
+// path runs in the kernels included below; nothing here falls back to host computation.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/adapt_mi355.h"
+#include "elementwise.hpp"
+#include "lut_rows.hpp"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                                  \
+    do {                                                                                               \
+        hipError_t e_ = (expr);                                                                        \
+        if (e_ != hipSuccess)                                                                          \
+            return fail(e_ == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "%s: %s", \
+                        #expr, hipGetErrorString(e_));                                                 \
+    } while (0)
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline unsigned ew_grid(size_t work_items) {
+    size_t g = (work_items + adapt::EW_THREADS - 1) / adapt::EW_THREADS;
+    if (g < 1) g = 1;
+    if (g > 256 * 16) g = 256 * 16;   // grid-stride loops: 16 blocks per compute unit is plenty
+    return (unsigned)g;
+}
+
+}  // namespace
+
+struct adapt_lut {
+    int bits;
+    int storage;            // 0: one signed 16-bit image; 1: low (unsigned) + high (signed) images
+    int32_t min_entry, max_entry;
+    int device;
+    int rs;                 // entries per image row = 2^b + 2
+    int img_bytes;          // per image, multiple of 16
+    uint16_t *img_dev[2];   // [0] = only / low half, [1] = high half
+};
+
+extern "C" {
+
+const char *adapt_last_error(void) { return g_err; }
+
+int adapt_device_cu_count(void) {
+    int dev = 0, cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(ADAPT_ERR_HIP, "hipGetDevice failed");
+    if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        return fail(ADAPT_ERR_HIP, "hipDeviceGetAttribute failed");
+    return cu;
+}
+
+int adapt_lut_create(adapt_lut **out, int bits, const int32_t *table_host) {
+    if (!out) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lut_create: out is NULL");
+    *out = nullptr;
+    if (!table_host) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lut_create: table_host is NULL");
+    if (bits < 2 || bits > 8) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lut_create: bits=%d not in [2,8]", bits);
+    const int n = 1 << bits;
+    int32_t lo = table_host[0], hi = table_host[0];
+    for (int i = 0; i < n * n; ++i) {
+        if (table_host[i] < lo) lo = table_host[i];
+        if (table_host[i] > hi) hi = table_host[i];
+    }
+    adapt_lut *l = new (std::nothrow) adapt_lut();
+    if (!l) return fail(ADAPT_ERR_OUT_OF_MEMORY, "adapt_lut_create: host allocation failed");
+    l->bits = bits;
+    l->min_entry = lo;
+    l->max_entry = hi;
+    l->storage = (lo >= -32768 && hi <= 32767) ? 0 : 1;
+    l->rs = n + 2;
+    l->img_bytes = ((n * l->rs * 2 + 15) / 16) * 16;
+    l->img_dev[0] = l->img_dev[1] = nullptr;
+    if (hipGetDevice(&l->device) != hipSuccess) {
+        delete l;
+        return fail(ADAPT_ERR_HIP, "adapt_lut_create: hipGetDevice failed");
+    }
+    // private image order: row = weight operand, column = activation operand, then a zero column
+    std::vector<uint16_t> img((size_t)l->img_bytes / 2, 0);
+    for (int half = 0; half <= l->storage; ++half) {
+        for (int w = 0; w < n; ++w)
+            for (int a = 0; a < n; ++a) {
+                const uint32_t v = (uint32_t)table_host[(size_t)a * n + w];
+                uint16_t e;
+                if (l->storage == 0) e = (uint16_t)v;
+                else e = half == 0 ? (uint16_t)(v & 0xffffu) : (uint16_t)(v >> 16);
+                img[(size_t)w * l->rs + a] = e;
+            }
+        hipError_t e = hipMalloc((void **)&l->img_dev[half], (size_t)l->img_bytes);
+        if (e == hipSuccess) e = hipMemcpy(l->img_dev[half], img.data(), (size_t)l->img_bytes, hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            for (int j = 0; j < 2; ++j)
+                if (l->img_dev[j]) (void)hipFree(l->img_dev[j]);
+            delete l;
+            return fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP,
+                        "adapt_lut_create: device image: %s", hipGetErrorString(e));
+        }
+    }
+    *out = l;
+    return ADAPT_OK;
+}
+
+int adapt_lut_destroy(adapt_lut *lut) {
+    if (!lut) return ADAPT_OK;
+    for (int j = 0; j < 2; ++j)
+        if (lut->img_dev[j]) (void)hipFree(lut->img_dev[j]);
+    delete lut;
+    return ADAPT_OK;
+}
+
+int adapt_lut_info(const adapt_lut *lut, int *bits, int *storage, int32_t *min_entry, int32_t *max_entry) {
+    if (!lut) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lut_info: lut is NULL");
+    if (bits) *bits = lut->bits;
+    if (storage) *storage = lut->storage;
+    if (min_entry) *min_entry = lut->min_entry;
+    if (max_entry) *max_entry = lut->max_entry;
+    return ADAPT_OK;
+}
+
+/* ------------------------------------------------------------------ quantiser / dequantiser */
+
+int adapt_absmax_f32(const float *x_dev, size_t n, float *amax_dev, void *stream) {
+    if (!amax_dev || (!x_dev && n)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_absmax_f32: NULL pointer");
+    hipStream_t s = (hipStream_t)stream;
+    adapt::fill_u32_kernel<<<1, 64, 0, s>>>(reinterpret_cast<uint32_t *>(amax_dev), 0u, 1);
+    if (n) {
+        const int vec = aligned16(x_dev) ? 1 : 0;
+        adapt::absmax_kernel<<<ew_grid(n / 8 + 1), adapt::EW_THREADS, 0, s>>>(x_dev, n, reinterpret_cast<uint32_t *>(amax_dev), vec);
+    }
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+int adapt_quantize_f32(const float *x_dev, int8_t *q_dev, size_t n, float scale, int bits, void *stream) {
+    if ((!x_dev || !q_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_quantize_f32: NULL pointer");
+    if (bits < 2 || bits > 8) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_quantize_f32: bits=%d not in [2,8]", bits);
+    if (!(scale > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_quantize_f32: scale must be > 0");
+    if (n == 0) return ADAPT_OK;
+    const int vec = (aligned16(x_dev) && aligned16(q_dev)) ? 1 : 0;
+    const float Q = (float)((1 << (bits - 1)) - 1);
+    adapt::quantize_kernel<<<ew_grid(n / 16 + 1), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, q_dev, n, scale, Q, vec);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+int adapt_dequant_i32(const int32_t *acc_dev, float *y_dev, size_t outer, size_t channels, size_t inner,
+                      float scale, const float *bias_dev, void *stream) {
+    const size_t n = outer * channels * inner;
+    if ((!acc_dev || !y_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_dequant_i32: NULL pointer");
+    if (n == 0) return ADAPT_OK;
+    const int vec = (aligned16(acc_dev) && aligned16(y_dev) && (!bias_dev || inner % 4 == 0)) ? 1 : 0;
+    adapt::dequant_kernel<<<ew_grid(n / 4 + 1), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(acc_dev, y_dev, n, channels, inner, scale, bias_dev, vec);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+}  // extern "C"
+
+/* ------------------------------------------------------------------ table-lookup matrix products */
+
+namespace {
+
+template <int NT, bool SIGNED>
+int launch_rows_inst(const adapt::RowsParams &p, dim3 grid, size_t lds, hipStream_t s) {
+    static size_t configured = 0;   // largest dynamic LDS size announced for this instantiation
+    auto kern = adapt::lut_rows_kernel<NT, SIGNED>;
+    if (lds > configured) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        configured = lds;
+    }
+    kern<<<grid, adapt::ROWS_THREADS, lds, s>>>(p);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+struct Geometry {
+    int mode;
+    int M, N, Cin, taps, kw;
+    int H, W, Wo, HoWo;
+    int sh, sw, ph, pw, dh, dw;
+    int kstride, img_stride;
+};
+
+// Run the rows kernel once per table image of the handle.
+int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *out, const Geometry &g, hipStream_t s) {
+    const int bits = lut->bits;
+    const long long Ktot = (long long)g.taps * g.Cin;
+    if (g.M == 0 || g.N == 0) return ADAPT_OK;
+    if (Ktot == 0) {
+        const size_t n = (size_t)g.M * g.N;
+        adapt::fill_u32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(reinterpret_cast<uint32_t *>(out), 0u, n);
+        HIP_TRY(hipGetLastError());
+        return ADAPT_OK;
+    }
+    // tile shape: prefer 16 outputs per lane; shrink the tile until the grid covers the chip
+    int cu = 256;
+    {
+        int dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
+    }
+    int NT = 16, MT = 1024;
+    auto groups = [&](int nt, int mt) { return (long long)((g.M + mt - 1) / mt) * ((g.N + nt - 1) / nt); };
+    while (MT > 64 && (MT / 2 >= g.M || (groups(NT, MT) < cu && Ktot / (adapt::ROWS_THREADS / (MT / 2)) >= 16))) MT /= 2;
+    if (groups(NT, MT) < cu && g.N > 8) NT = 8;
+    const int KS = adapt::ROWS_THREADS / MT;
+    const int Npad = ((g.N + NT - 1) / NT) * NT;
+
+    uint32_t *wofs = nullptr;
+    HIP_TRY(hipMallocAsync((void **)&wofs, (size_t)Ktot * Npad * sizeof(uint32_t), s));
+    const size_t pack_n = (size_t)Ktot * Npad;
+    adapt::pack_row_offsets_kernel<<<(unsigned)((pack_n + 255) / 256), 256, 0, s>>>(
+        w, wofs, (int)Ktot, g.N, Npad, g.Cin, g.taps, g.mode, 1 << (bits - 1), (1 << bits) - 1, lut->rs * 2);
+    hipError_t pe = hipGetLastError();
+    int rc = ADAPT_OK;
+    if (pe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "pack_row_offsets launch: %s", hipGetErrorString(pe));
+
+    adapt::RowsParams p;
+    p.x = x; p.wofs = wofs; p.out = out;
+    p.img_bytes = lut->img_bytes;
+    p.M = g.M; p.N = g.N; p.Npad = Npad; p.mode = g.mode; p.Cin = g.Cin; p.taps = g.taps; p.kw = g.kw;
+    p.H = g.H; p.W = g.W; p.Wo = g.Wo; p.HoWo = g.HoWo;
+    p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.dh = g.dh; p.dw = g.dw;
+    p.kstride = g.kstride; p.img_stride = g.img_stride;
+    p.hoff = 1 << (bits - 1); p.mask = (1 << bits) - 1;
+    p.a_zero2 = (1 << (bits - 1)) * 2; p.a_skip2 = (1 << bits) * 2;
+    p.MT = MT; p.KS = KS;
+    dim3 grid((unsigned)((g.M + MT - 1) / MT), (unsigned)(Npad / NT));
+    size_t lds = (size_t)lut->img_bytes;
+    if (KS > 1 && (size_t)adapt::ROWS_THREADS * NT * 4 > lds) lds = (size_t)adapt::ROWS_THREADS * NT * 4;
+    for (int half = 0; half <= lut->storage && rc == ADAPT_OK; ++half) {
+        p.img = lut->img_dev[half];
+        p.shift = half == 0 ? -1 : 16;
+        const bool sgn = (lut->storage == 0) || half == 1;
+        if (NT == 16) rc = sgn ? launch_rows_inst<16, true>(p, grid, lds, s) : launch_rows_inst<16, false>(p, grid, lds, s);
+        else rc = sgn ? launch_rows_inst<8, true>(p, grid, lds, s) : launch_rows_inst<8, false>(p, grid, lds, s);
+    }
+    hipError_t fe = hipFreeAsync(wofs, s);
+    if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
+    return rc;
+}
+
+int check_lut(const adapt_lut *lut, const char *who) {
+    if (!lut) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: lut is NULL", who);
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != lut->device)
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: table handle belongs to device %d, current device is %d", who, lut->device, dev);
+    return ADAPT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int adapt_approx_linear(const adapt_lut *lut, const int8_t *a_dev, const int8_t *w_dev, int32_t *acc_dev, int M,
+                        int K, int N, void *stream) {
+    int rc = check_lut(lut, "adapt_approx_linear");
+    if (rc) return rc;
+    if (M < 0 || K < 0 || N < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_linear: negative dimension");
+    if (M == 0 || N == 0) return ADAPT_OK;
+    if (!acc_dev || (K > 0 && (!a_dev || !w_dev))) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_linear: NULL pointer");
+    if ((long long)M * N > 0x7fffffffLL || (long long)M * K > 0x7fffffffLL || (long long)N * K > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "adapt_approx_linear: tensor with more than 2^31-1 elements");
+    Geometry g{};
+    g.mode = adapt::MODE_GEMM; g.M = M; g.N = N; g.Cin = K; g.taps = 1; g.kw = 1;
+    g.H = 1; g.W = 1; g.Wo = 1; g.HoWo = 1; g.sh = g.sw = g.dh = g.dw = 1; g.ph = g.pw = 0;
+    g.kstride = 1; g.img_stride = K;
+    return run_rows(lut, a_dev, w_dev, acc_dev, g, (hipStream_t)stream);
+}
+
+int adapt_approx_conv2d(const adapt_lut *lut, const int8_t *x_dev, const int8_t *w_dev, int32_t *acc_dev, int N,
+                        int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w, int pad_h,
+                        int pad_w, int dil_h, int dil_w, int groups, void *stream) {
+    int rc = check_lut(lut, "adapt_approx_conv2d");
+    if (rc) return rc;
+    if (N < 0 || Cin < 1 || H < 1 || W < 1 || Cout < 1 || kh < 1 || kw < 1 || stride_h < 1 || stride_w < 1 ||
+        pad_h < 0 || pad_w < 0 || dil_h < 1 || dil_w < 1 || groups < 1)
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_conv2d: bad dimension");
+    if (Cin % groups || Cout % groups) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_conv2d: channels not divisible by groups");
+    if (groups != 1) return fail(ADAPT_ERR_UNSUPPORTED, "adapt_approx_conv2d: groups=%d (only 1 in this build)", groups);
+    const long long Ho = ((long long)H + 2LL * pad_h - (long long)dil_h * (kh - 1) - 1) / stride_h + 1;
+    const long long Wo = ((long long)W + 2LL * pad_w - (long long)dil_w * (kw - 1) - 1) / stride_w + 1;
+    if ((long long)H + 2LL * pad_h - (long long)dil_h * (kh - 1) - 1 < 0 || (long long)W + 2LL * pad_w - (long long)dil_w * (kw - 1) - 1 < 0)
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_conv2d: filter larger than padded input");
+    if (N == 0) return ADAPT_OK;
+    if (!x_dev || !w_dev || !acc_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_conv2d: NULL pointer");
+    if ((long long)N * Cout * Ho * Wo > 0x7fffffffLL || (long long)N * Cin * H * W > 0x7fffffffLL ||
+        (long long)N * Ho * Wo > 0x7fffffffLL || (long long)Cout * Cin * kh * kw > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "adapt_approx_conv2d: tensor with more than 2^31-1 elements");
+    Geometry g{};
+    g.mode = adapt::MODE_CONV; g.M = (int)(N * Ho * Wo); g.N = Cout; g.Cin = Cin; g.taps = kh * kw; g.kw = kw;
+    g.H = H; g.W = W; g.Wo = (int)Wo; g.HoWo = (int)(Ho * Wo);
+    g.sh = stride_h; g.sw = stride_w; g.ph = pad_h; g.pw = pad_w; g.dh = dil_h; g.dw = dil_w;
+    g.kstride = H * W; g.img_stride = Cin * H * W;
+    return run_rows(lut, x_dev, w_dev, acc_dev, g, (hipStream_t)stream);
+}
+
+int adapt_approx_conv_transpose2d(const adapt_lut *lut, const int8_t *x_dev, const int8_t *w_dev, int32_t *acc_dev,
+                                  int N, int Cin, int H, int W, int Cout, int kh, int kw, int stride, int pad,
+                                  void *stream) {
+    int rc = check_lut(lut, "adapt_approx_conv_transpose2d");
+    if (rc) return rc;
+    if (N < 0 || Cin < 1 || H < 1 || W < 1 || Cout < 1 || kh < 1 || kw < 1 || stride < 1 || pad < 0)
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_conv_transpose2d: bad dimension");
+    const long long Ho = ((long long)H - 1) * stride - 2LL * pad + kh, Wo = ((long long)W - 1) * stride - 2LL * pad + kw;
+    if (Ho < 1 || Wo < 1) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_conv_transpose2d: empty output");
+    if (N == 0) return ADAPT_OK;
+    if (!x_dev || !w_dev || !acc_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_conv_transpose2d: NULL pointer");
+    if ((long long)N * Cout * Ho * Wo > 0x7fffffffLL || (long long)N * Cin * H * W > 0x7fffffffLL ||
+        (long long)Cout * Cin * kh * kw > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "adapt_approx_conv_transpose2d: tensor with more than 2^31-1 elements");
+    Geometry g{};
+    g.mode = adapt::MODE_CONVT; g.M = (int)(N * Ho * Wo); g.N = Cout; g.Cin = Cin; g.taps = kh * kw; g.kw = kw;
+    g.H = H; g.W = W; g.Wo = (int)Wo; g.HoWo = (int)(Ho * Wo);
+    g.sh = stride; g.sw = stride; g.ph = pad; g.pw = pad; g.dh = g.dw = 1;
+    g.kstride = H * W; g.img_stride = Cin * H * W;
+    return run_rows(lut, x_dev, w_dev, acc_dev, g, (hipStream_t)stream);
+}
+
+/* ------------------------------------------------------------------ fp32 operations between layers */
+
+int adapt_relu_f32(const float *x_dev, float *y_dev, size_t n, void *stream) {
+    if ((!x_dev || !y_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_relu_f32: NULL pointer");
+    if (!n) return ADAPT_OK;
+    adapt::relu_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, y_dev, n);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+int adapt_add_f32(const float *a_dev, const float *b_dev, float *y_dev, size_t n, int relu, void *stream) {
+    if ((!a_dev || !b_dev || !y_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_add_f32: NULL pointer");
+    if (!n) return ADAPT_OK;
+    adapt::add_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(a_dev, b_dev, y_dev, n, relu);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+int adapt_avgpool_hw_f32(const float *x_dev, float *y_dev, size_t NC, size_t HW, void *stream) {
+    if ((!x_dev || !y_dev) && NC) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_avgpool_hw_f32: NULL pointer");
+    if (HW == 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_avgpool_hw_f32: HW is 0");
+    if (!NC) return ADAPT_OK;
+    adapt::avgpool_kernel<<<(unsigned)((NC + adapt::EW_THREADS - 1) / adapt::EW_THREADS), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, y_dev, NC, HW);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+int adapt_shortcut_a_f32(const float *x_dev, float *y_dev, int N, int Cin, int H, int W, int Cout, void *stream) {
+    if (N < 0 || Cin < 1 || H < 1 || W < 1 || Cout < Cin) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_shortcut_a_f32: bad dimension");
+    if (N == 0) return ADAPT_OK;
+    if (!x_dev || !y_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_shortcut_a_f32: NULL pointer");
+    if (x_dev == y_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_shortcut_a_f32: in-place not possible");
+    const size_t total = (size_t)N * Cout * ((H + 1) / 2) * ((W + 1) / 2);
+    adapt::shortcut_a_kernel<<<ew_grid(total), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, y_dev, N, Cin, H, W, Cout);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+static int unary(const float *x_dev, float *y_dev, size_t n, int op, void *stream, const char *who) {
+    if ((!x_dev || !y_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
+    if (!n) return ADAPT_OK;
+    adapt::unary_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, y_dev, n, op);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+int adapt_tanh_f32(const float *x_dev, float *y_dev, size_t n, void *stream) { return unary(x_dev, y_dev, n, 0, stream, "adapt_tanh_f32"); }
+int adapt_sigmoid_f32(const float *x_dev, float *y_dev, size_t n, void *stream) { return unary(x_dev, y_dev, n, 1, stream, "adapt_sigmoid_f32"); }
+
+int adapt_lstm_cell_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh,
+                        const float *bias_dev, float *c_dev, float *h_dev, int B, int Hs, void *stream) {
+    if (B < 0 || Hs < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lstm_cell_f32: negative dimension");
+    const size_t n = (size_t)B * Hs;
+    if (!n) return ADAPT_OK;
+    if (!acc_ih_dev || !acc_hh_dev || !c_dev || !h_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lstm_cell_f32: NULL pointer");
+    adapt::lstm_cell_kernel<<<(unsigned)((n + adapt::EW_THREADS - 1) / adapt::EW_THREADS), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(
+        acc_ih_dev, acc_hh_dev, s_ih, s_hh, bias_dev, c_dev, h_dev, B, Hs);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,223 @@
+// HBM-bound kernels of the path: max-abs calibration, quantiser, dequantiser (Sec. III-A of the
+// paper) and the fp32 operations between approximate layers (Sec. III-B "RNN Layer" memory cell,
+// residual adds, pooling).  gfx950 only; compiled with -ffp-contract=off so that every fp32 step
+// rounds exactly where the text says it does.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace adapt {
+
+constexpr int EW_THREADS = 256;
+
+__global__ void fill_u32_kernel(uint32_t *p, uint32_t v, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// max |x|: the bit pattern of a non-negative float orders like an unsigned integer, so the final
+// combine is an integer atomic max; NaNs fail the comparison and are skipped.
+__global__ __launch_bounds__(EW_THREADS) void absmax_kernel(const float *__restrict__ x, size_t n,
+                                                            uint32_t *__restrict__ out_bits, int vec) {
+    float m = 0.0f;
+    const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    const size_t n4 = vec ? n / 4 : 0;   // vec: x is 16-byte aligned
+    const float4 *x4 = reinterpret_cast<const float4 *>(x);
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n4; i += stride) {
+        const float4 v = x4[i];
+        float a = fabsf(v.x); if (a > m) m = a;
+        a = fabsf(v.y); if (a > m) m = a;
+        a = fabsf(v.z); if (a > m) m = a;
+        a = fabsf(v.w); if (a > m) m = a;
+    }
+    for (size_t i = n4 * 4 + (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
+        const float a = fabsf(x[i]);
+        if (a > m) m = a;
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const float o = __shfl_xor(m, off, 64);
+        if (o > m) m = o;
+    }
+    if ((threadIdx.x & 63) == 0) atomicMax(out_bits, __float_as_uint(m));
+}
+
+__device__ __forceinline__ int quant1(float x, float scale, float Q) {
+    float r = rintf(x / scale);          // IEEE divide, round half to even
+    if (r != r) r = 0.0f;
+    if (r > Q) r = Q;
+    if (r < -Q) r = -Q;
+    return (int)r;
+}
+
+__global__ __launch_bounds__(EW_THREADS) void quantize_kernel(const float *__restrict__ x, int8_t *__restrict__ q,
+                                                              size_t n, float scale, float Q, int vec) {
+    // 16 values per thread step: four 16-byte loads, one 16-byte store (vec: both pointers 16-byte aligned)
+    const size_t n16 = vec ? n / 16 : 0;
+    const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    const float4 *x4 = reinterpret_cast<const float4 *>(x);
+    uint4 *q16 = reinterpret_cast<uint4 *>(q);
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n16; i += stride) {
+        uint32_t w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float4 v = x4[i * 4 + j];
+            const uint32_t b0 = (uint32_t)quant1(v.x, scale, Q) & 0xffu;
+            const uint32_t b1 = (uint32_t)quant1(v.y, scale, Q) & 0xffu;
+            const uint32_t b2 = (uint32_t)quant1(v.z, scale, Q) & 0xffu;
+            const uint32_t b3 = (uint32_t)quant1(v.w, scale, Q) & 0xffu;
+            w[j] = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
+        }
+        q16[i] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    for (size_t i = n16 * 16 + (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride)
+        q[i] = (int8_t)quant1(x[i], scale, Q);
+}
+
+// y = float(acc) * scale (+ bias[c]); channel of flat index i is (i / inner) % channels
+__global__ __launch_bounds__(EW_THREADS) void dequant_kernel(const int32_t *__restrict__ acc, float *__restrict__ y,
+                                                             size_t n, size_t channels, size_t inner, float scale,
+                                                             const float *__restrict__ bias, int vec) {
+    const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    // vec: both pointers 16-byte aligned and four consecutive elements share one channel (or no bias)
+    if (vec) {
+        const size_t n4 = n / 4;
+        const int4 *a4 = reinterpret_cast<const int4 *>(acc);
+        float4 *y4 = reinterpret_cast<float4 *>(y);
+        for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n4; i += stride) {
+            const int4 a = a4[i];
+            float4 v;
+            v.x = (float)a.x * scale; v.y = (float)a.y * scale; v.z = (float)a.z * scale; v.w = (float)a.w * scale;
+            if (bias) {
+                const float b = bias[((i * 4) / inner) % channels];
+                v.x = v.x + b; v.y = v.y + b; v.z = v.z + b; v.w = v.w + b;
+            }
+            y4[i] = v;
+        }
+        for (size_t i = n4 * 4 + (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
+            float v = (float)acc[i] * scale;
+            if (bias) v = v + bias[(i / inner) % channels];
+            y[i] = v;
+        }
+    } else {
+        for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
+            float v = (float)acc[i] * scale;
+            if (bias) v = v + bias[(i / inner) % channels];
+            y[i] = v;
+        }
+    }
+}
+
+__global__ __launch_bounds__(EW_THREADS) void relu_kernel(const float *x, float *y, size_t n) {
+    const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
+        const float v = x[i];
+        y[i] = v > 0.0f ? v : 0.0f;
+    }
+}
+
+__global__ __launch_bounds__(EW_THREADS) void add_kernel(const float *a, const float *b, float *y, size_t n, int relu) {
+    const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
+        float v = a[i] + b[i];
+        if (relu) v = v > 0.0f ? v : 0.0f;
+        y[i] = v;
+    }
+}
+
+// one thread per (n, c) plane: the sum order (row-major, sequential) is part of the definition
+__global__ __launch_bounds__(EW_THREADS) void avgpool_kernel(const float *__restrict__ x, float *__restrict__ y,
+                                                             size_t NC, size_t HW) {
+    const size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (i >= NC) return;
+    const float inv = 1.0f / (float)HW;
+    float s = 0.0f;
+    for (size_t j = 0; j < HW; ++j) s = s + x[i * HW + j];
+    y[i] = s * inv;
+}
+
+__global__ __launch_bounds__(EW_THREADS) void shortcut_a_kernel(const float *__restrict__ x, float *__restrict__ y,
+                                                                int N, int Cin, int H, int W, int Cout) {
+    const int Ho = (H + 1) / 2, Wo = (W + 1) / 2, padc = (Cout - Cin) / 2;
+    const size_t total = (size_t)N * Cout * Ho * Wo;
+    const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < total; i += stride) {
+        const int ox = (int)(i % Wo);
+        const int oy = (int)((i / Wo) % Ho);
+        const int c = (int)((i / ((size_t)Wo * Ho)) % Cout);
+        const int n = (int)(i / ((size_t)Wo * Ho * Cout));
+        const int ci = c - padc;
+        float v = 0.0f;
+        if (ci >= 0 && ci < Cin) v = x[(((size_t)n * Cin + ci) * H + 2 * oy) * W + 2 * ox];
+        y[i] = v;
+    }
+}
+
+// exp(x) written out so that host and device agree bit for bit: clamp to [-87, 88];
+// n = rint(x * log2 e); r = x - n ln2 in two fused steps (hi/lo split of ln 2); degree-7 Taylor
+// polynomial in Horner form, fused multiply-adds; exact scaling by 2^n.
+__device__ __forceinline__ float exp_spec(float x) {
+    const float LOG2E = 0x1.715476p+0f, LN2_HI = 0x1.62e400p-1f, LN2_LO = 0x1.7f7d1cp-20f;
+    if (x != x) return x;
+    if (x < -87.0f) x = -87.0f;
+    if (x > 88.0f) x = 88.0f;
+    const float n = rintf(x * LOG2E);
+    float r = __builtin_fmaf(n, -LN2_HI, x);
+    r = __builtin_fmaf(n, -LN2_LO, r);
+    float p = 0x1.a01a02p-13f;
+    p = __builtin_fmaf(p, r, 0x1.6c16c2p-10f);
+    p = __builtin_fmaf(p, r, 0x1.111112p-7f);
+    p = __builtin_fmaf(p, r, 0x1.555556p-5f);
+    p = __builtin_fmaf(p, r, 0x1.555556p-3f);
+    p = __builtin_fmaf(p, r, 0.5f);
+    p = __builtin_fmaf(p, r, 1.0f);
+    p = __builtin_fmaf(p, r, 1.0f);
+    return ldexpf(p, (int)n);
+}
+
+__device__ __forceinline__ float sigmoid_spec(float x) { return 1.0f / (1.0f + exp_spec(-x)); }
+
+__device__ __forceinline__ float tanh_spec(float x) {
+    const float ax = fabsf(x);
+    const float e = exp_spec(-2.0f * ax);
+    const float t = (1.0f - e) / (1.0f + e);
+    return x < 0.0f ? -t : t;
+}
+
+__global__ __launch_bounds__(EW_THREADS) void unary_kernel(const float *x, float *y, size_t n, int op) {
+    const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
+        const float v = x[i];
+        y[i] = op == 0 ? tanh_spec(v) : (op == 1 ? sigmoid_spec(v) : exp_spec(v));
+    }
+}
+
+__global__ __launch_bounds__(EW_THREADS) void lstm_cell_kernel(const int32_t *__restrict__ acc_ih,
+                                                               const int32_t *__restrict__ acc_hh, float s_ih,
+                                                               float s_hh, const float *__restrict__ bias,
+                                                               float *__restrict__ c, float *__restrict__ h, int B,
+                                                               int Hs) {
+    const size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (i >= (size_t)B * Hs) return;
+    const int b = (int)(i / Hs), j = (int)(i % Hs);
+    float pre[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const size_t idx = (size_t)b * 4 * Hs + (size_t)g * Hs + j;
+        const float u = (float)acc_ih[idx] * s_ih;
+        const float v = (float)acc_hh[idx] * s_hh;
+        float s = u + v;
+        s = s + (bias ? bias[g * Hs + j] : 0.0f);
+        pre[g] = s;
+    }
+    const float ig = sigmoid_spec(pre[0]);
+    const float fg = sigmoid_spec(pre[1]);
+    const float gg = tanh_spec(pre[2]);
+    const float og = sigmoid_spec(pre[3]);
+    const float fc = fg * c[i];
+    const float igg = ig * gg;
+    const float cn = fc + igg;
+    c[i] = cn;
+    h[i] = og * tanh_spec(cn);
+}
+
+}  // namespace adapt

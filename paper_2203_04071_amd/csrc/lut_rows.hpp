@@ -1,0 +1,188 @@
+// General table-lookup matrix-product kernel ("rows" kernel): the whole 2^b x 2^b multiplier table
+// sits in LDS and every inner-product term is one 16-bit LDS read (Sec. IV of the paper: the inner
+// multiplications are table look-ups; its AVX2 gather becomes a per-lane LDS gather here).
+//
+// Mapping (gfx950, 64-wide waves): lanes run along the rows of the expanded input matrix (batch x
+// output pixels), because that is the long dimension of every layer shape; the weight of a term is
+// wave-uniform, so the byte offset of its table row comes from a scalar load of a pre-packed
+// offset array and the per-lane part of the address is just the activation.  The LDS image is
+// stored weight-major, image[w][a], so that all lanes of one lookup fall into one row: at most
+// 2^b/2 distinct bank words, identical activations broadcast.
+//
+// One kernel serves linear layers, convolutions (implicit expansion, padded taps are looked up with
+// activation 0) and transposed convolutions in gather form (taps without a real input pixel read an
+// all-zero extra column, so they add nothing).  Short matrices split K over the waves of a
+// workgroup and reduce through LDS.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace adapt {
+
+constexpr int ROWS_THREADS = 1024;
+
+enum { MODE_GEMM = 0, MODE_CONV = 1, MODE_CONVT = 2 };
+
+struct RowsParams {
+    const int8_t *x;        // activations: [M][K] or NCHW
+    const uint32_t *wofs;   // [Ktot][Npad] byte offset of the table row of weight (k, n); k = tap * Cin + ci
+    int32_t *out;           // [M][N] or NCHW
+    const uint16_t *img;    // table image: 2^b rows (one per weight) of RS = 2^b + 2 entries
+    int img_bytes;          // multiple of 16
+    int M, N, Npad;
+    int mode;
+    int Cin;                // inner length per tap (GEMM: K)
+    int taps, kw;           // kh * kw (GEMM: 1)
+    int H, W, Wo, HoWo;     // GEMM: HoWo = Wo = 1
+    int sh, sw, ph, pw, dh, dw;
+    int kstride;            // elements between consecutive ci of one row (GEMM 1, conv H * W)
+    int img_stride;         // elements per image of x (GEMM: K)
+    int hoff, mask;         // H = 2^(b-1), 2^b - 1
+    int a_zero2, a_skip2;   // byte offset in a table row of activation 0 / of the all-zero column
+    int MT, KS;             // rows per workgroup, K slices per workgroup; MT * KS == ROWS_THREADS
+    int shift;              // < 0: out = acc;  >= 0: out += acc << shift (second half of a split table)
+};
+
+// weights -> byte offsets of their table rows, in the order the kernel walks K
+__global__ void pack_row_offsets_kernel(const int8_t *__restrict__ w, uint32_t *__restrict__ wofs, int Ktot,
+                                        int N, int Npad, int Cin, int taps, int mode, int hoff, int mask,
+                                        int row_bytes) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)Ktot * Npad) return;
+    const int k = (int)(idx / Npad), n = (int)(idx % Npad);
+    uint32_t v = 0;
+    if (n < N) {
+        const int t = k / Cin, ci = k - t * Cin;
+        size_t wi;
+        if (mode == MODE_CONVT) wi = ((size_t)ci * N + n) * taps + t;      // [Cin][Cout][kh][kw]
+        else wi = ((size_t)n * Cin + ci) * taps + t;                       // [N][K] / [Cout][Cin][kh][kw]
+        v = (uint32_t)(((int)w[wi] + hoff) & mask) * (uint32_t)row_bytes;
+    }
+    wofs[idx] = v;
+}
+
+template <bool SIGNED>
+__device__ __forceinline__ uint32_t lds_entry(const unsigned char *smem, uint32_t off) {
+    if (SIGNED) return (uint32_t)(int32_t) * reinterpret_cast<const int16_t *>(smem + off);
+    return (uint32_t) * reinterpret_cast<const uint16_t *>(smem + off);
+}
+
+template <int NT, bool SIGNED>
+__global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams p) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    {   // stage the table image
+        const uint4 *src = reinterpret_cast<const uint4 *>(p.img);
+        uint4 *dst = reinterpret_cast<uint4 *>(smem);
+        const int n16 = p.img_bytes >> 4;
+        for (int i = tid; i < n16; i += ROWS_THREADS) dst[i] = src[i];
+    }
+    __syncthreads();
+
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int row_waves = p.MT >> 6;
+    const int ks = wave / row_waves;
+    const int rb = wave - ks * row_waves;
+    const int r_in_tile = rb * 64 + lane;
+    const int m = blockIdx.x * p.MT + r_in_tile;
+    const bool mvalid = m < p.M;
+    const int mm = mvalid ? m : p.M - 1;
+    const int n0 = blockIdx.y * NT;
+
+    const int img = mm / p.HoWo;
+    const int pix = mm - img * p.HoWo;
+    const int oy = pix / p.Wo;
+    const int ox = pix - oy * p.Wo;
+    const int8_t *xb = p.x + (size_t)img * p.img_stride;
+
+    const int Ktot = p.taps * p.Cin;
+    const int kc = (Ktot + p.KS - 1) / p.KS;
+    int k = ks * kc;
+    const int k_end = min(Ktot, k + kc);
+
+    uint32_t acc[NT];
+#pragma unroll
+    for (int n = 0; n < NT; ++n) acc[n] = 0;
+
+    while (k < k_end) {
+        const int t = k / p.Cin;
+        const int c0 = k - t * p.Cin;
+        const int cnt = min(p.Cin - c0, k_end - k);
+        int base = 0;
+        bool valid = true;
+        if (p.mode == MODE_CONV) {
+            const int ky = t / p.kw, kx = t - ky * p.kw;
+            const int iy = oy * p.sh - p.ph + ky * p.dh, ix = ox * p.sw - p.pw + kx * p.dw;
+            valid = (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+            base = iy * p.W + ix;
+        } else if (p.mode == MODE_CONVT) {
+            const int ky = t / p.kw, kx = t - ky * p.kw;
+            const int ty = oy + p.ph - ky, tx = ox + p.pw - kx;
+            const int iy = ty / p.sh, ix = tx / p.sw;
+            valid = ty >= 0 && tx >= 0 && iy * p.sh == ty && ix * p.sw == tx && iy < p.H && ix < p.W;
+            base = iy * p.W + ix;
+        }
+        const int fill2 = (p.mode == MODE_CONVT) ? p.a_skip2 : p.a_zero2;
+        const int8_t *xp = xb + (valid ? base : 0) + (size_t)c0 * p.kstride;
+        const uint32_t *wr = p.wofs + (size_t)k * p.Npad + n0;
+        int c = 0;
+        for (; c + 4 <= cnt; c += 4) {
+            uint32_t a2[4];
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const int a = xp[(size_t)(c + kk) * p.kstride];
+                a2[kk] = valid ? (uint32_t)(((a + p.hoff) & p.mask) << 1) : (uint32_t)fill2;
+            }
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const uint32_t *w4 = wr + (size_t)(c + kk) * p.Npad;
+#pragma unroll
+                for (int n = 0; n < NT; ++n) acc[n] += lds_entry<SIGNED>(smem, w4[n] + a2[kk]);
+            }
+        }
+        for (; c < cnt; ++c) {
+            const int a = xp[(size_t)c * p.kstride];
+            const uint32_t a2 = valid ? (uint32_t)(((a + p.hoff) & p.mask) << 1) : (uint32_t)fill2;
+            const uint32_t *w1 = wr + (size_t)c * p.Npad;
+#pragma unroll
+            for (int n = 0; n < NT; ++n) acc[n] += lds_entry<SIGNED>(smem, w1[n] + a2);
+        }
+        k += cnt;
+    }
+
+    if (p.KS == 1) {
+        if (mvalid) {
+            int32_t *o = p.out + (size_t)img * p.N * p.HoWo + pix;
+#pragma unroll
+            for (int n = 0; n < NT; ++n) {
+                if (n0 + n < p.N) {
+                    int32_t *q = o + (size_t)(n0 + n) * p.HoWo;
+                    if (p.shift < 0) *q = (int32_t)acc[n];
+                    else *q = (int32_t)((uint32_t)*q + (acc[n] << p.shift));
+                }
+            }
+        }
+        return;
+    }
+
+    // K was split over the waves: reduce the partial sums through LDS (the table is no longer needed)
+    __syncthreads();
+    uint32_t *red = reinterpret_cast<uint32_t *>(smem);      // [KS][NT][MT]
+#pragma unroll
+    for (int n = 0; n < NT; ++n) red[((size_t)ks * NT + n) * p.MT + r_in_tile] = acc[n];
+    __syncthreads();
+    for (int o = tid; o < NT * p.MT; o += ROWS_THREADS) {
+        const int n = o / p.MT, r = o - n * p.MT;
+        const int m2 = blockIdx.x * p.MT + r;
+        if (m2 >= p.M || n0 + n >= p.N) continue;
+        uint32_t s = 0;
+        for (int j = 0; j < p.KS; ++j) s += red[((size_t)j * NT + n) * p.MT + r];
+        const int img2 = m2 / p.HoWo, pix2 = m2 - img2 * p.HoWo;
+        int32_t *q = p.out + (size_t)img2 * p.N * p.HoWo + (size_t)(n0 + n) * p.HoWo + pix2;
+        if (p.shift < 0) *q = (int32_t)s;
+        else *q = (int32_t)((uint32_t)*q + (s << p.shift));
+    }
+}
+
+}  // namespace adapt

@@ -1,0 +1,163 @@
+"""Network-shaped workloads (CNN, LSTM, GAN families of Sec. V, Table I) as sequences of C-ABI
+calls.  Every tensor operation is a library kernel; Python only orders the calls and holds the
+per-layer scales (plain floats) that max-abs calibration produced.
+
+Calibration (Sec. III-A, "max absolute number" scale) is progressive: the scale of a layer's
+input is the max-abs of the fp32 tensor that the already-approximate earlier layers produce on
+the calibration batch.  It needs one device->host read per layer and is therefore done once;
+`scales=` replays a calibrated network without any synchronisation.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .workloads import resnet20_plan
+
+
+def _f(x):
+    return np.float32(x)
+
+
+def scale_from_amax(amax: float, bits: int) -> np.float32:
+    q = _f((1 << (bits - 1)) - 1)
+    a = _f(amax)
+    return _f(1.0) if not (a > 0) else a / q
+
+
+def calibrated_scale(x, bits) -> np.float32:
+    return scale_from_amax(B.adapt_absmax_f32(x).item(), bits)
+
+
+def quantize_weights(w, bits):
+    s = calibrated_scale(w, bits)
+    return B.adapt_quantize_f32(w, s, bits), s
+
+
+class ResNet20:
+    def __init__(self, cfg, device="cuda"):
+        self.bits = cfg["bits"]
+        self.lut = B.Lut(cfg["lut"], self.bits)
+        self.plan = resnet20_plan()
+        self.qws = [quantize_weights(torch.from_numpy(w).to(device), self.bits) for w in cfg["convs"]]
+        self.qfw, self.s_fw = quantize_weights(torch.from_numpy(cfg["fc_w"]).to(device), self.bits)
+        self.fc_b = torch.from_numpy(cfg["fc_b"]).to(device)
+        self.scales = None
+        self.macs = None
+
+    def _conv(self, i, x, used, keep):
+        bits = self.bits
+        s_x = calibrated_scale(x, bits) if self.scales is None else self.scales[i]
+        used.append(s_x)
+        qx = B.adapt_quantize_f32(x, s_x, bits)
+        st = self.plan[i][2]
+        acc = B.adapt_approx_conv2d(self.lut, qx, self.qws[i][0], (st, st), (1, 1))
+        if keep is not None:
+            keep.append(acc)
+        n, c, h, w = acc.shape
+        return B.adapt_dequant_i32(acc, _f(s_x) * _f(self.qws[i][1]), n, c, h * w)
+
+    def forward(self, x, keep=None):
+        used = []
+        x = B.adapt_relu_f32(self._conv(0, x, used, keep))
+        i = 1
+        while i < len(self.plan):
+            cin, cout, stride = self.plan[i]
+            y = self._conv(i, x, used, keep)
+            B.adapt_relu_f32(y, out=y)
+            z = self._conv(i + 1, y, used, keep)
+            sc = x if (stride == 1 and cin == cout) else B.adapt_shortcut_a_f32(x, cout)
+            x = B.adapt_add_f32(z, sc, relu=True)
+            i += 2
+        pooled = B.adapt_avgpool_hw_f32(x)
+        s_p = calibrated_scale(pooled, self.bits) if self.scales is None else self.scales[len(self.plan)]
+        used.append(s_p)
+        qp = B.adapt_quantize_f32(pooled, s_p, self.bits)
+        acc = B.adapt_approx_linear(self.lut, qp, self.qfw)
+        logits = B.adapt_dequant_i32(acc, _f(s_p) * _f(self.s_fw), acc.shape[0], acc.shape[1], 1, self.fc_b)
+        if self.scales is None:
+            self.scales = used
+        return dict(logits=logits, fc_acc=acc, feat=x, scales=used)
+
+
+class LSTM:
+    def __init__(self, cfg, device="cuda"):
+        self.bits = cfg["bits"]
+        self.lut = B.Lut(cfg["lut"], self.bits)
+        self.q_wih, self.s_wih = quantize_weights(torch.from_numpy(cfg["w_ih"]).to(device), self.bits)
+        self.q_whh, self.s_whh = quantize_weights(torch.from_numpy(cfg["w_hh"]).to(device), self.bits)
+        self.bias = torch.from_numpy(cfg["bias"]).to(device)
+        self.Hs = cfg["w_hh"].shape[1]
+        self.s_x = None
+
+    def forward(self, x):
+        bits = self.bits
+        T, Bn, I = x.shape
+        Q = (1 << (bits - 1)) - 1
+        if self.s_x is None:
+            self.s_x = calibrated_scale(x, bits)          # over the whole [T, B, I] input
+        s_h = _f(1.0) / _f(Q)
+        qx = B.adapt_quantize_f32(x, self.s_x, bits).view(T * Bn, I)
+        acc_ih = B.adapt_approx_linear(self.lut, qx, self.q_wih).view(T, Bn, 4 * self.Hs)
+        hs = torch.empty((T, Bn, self.Hs), dtype=torch.float32, device=x.device)
+        h = torch.zeros((Bn, self.Hs), dtype=torch.float32, device=x.device)
+        c = torch.zeros((Bn, self.Hs), dtype=torch.float32, device=x.device)
+        qh = torch.empty((Bn, self.Hs), dtype=torch.int8, device=x.device)
+        acc_hh = torch.empty((Bn, 4 * self.Hs), dtype=torch.int32, device=x.device)
+        s_ih = _f(self.s_x) * _f(self.s_wih)
+        s_hh = _f(s_h) * _f(self.s_whh)
+        for t in range(T):
+            B.adapt_quantize_f32(h, s_h, bits, out=qh)
+            B.adapt_approx_linear(self.lut, qh, self.q_whh, out=acc_hh)
+            h = hs[t]
+            B.adapt_lstm_cell_f32(acc_ih[t], acc_hh, s_ih, s_hh, self.bias, c, h)
+        return dict(hs=hs, c=c, acc_ih=acc_ih, acc_hh_last=acc_hh, s_x=self.s_x, s_h=s_h)
+
+
+class DCGAN:
+    def __init__(self, cfg, device="cuda"):
+        self.bits = cfg["bits"]
+        self.lut = B.Lut(cfg["lut"], self.bits)
+        self.plan = cfg["plan"]
+        self.qws = [quantize_weights(torch.from_numpy(w).to(device), self.bits) for w in cfg["ws"]]
+        self.scales = None
+
+    def forward(self, z, keep=None):
+        used = []
+        x = z
+        nl = len(self.plan)
+        acc = None
+        for i, (cin, cout, s, p) in enumerate(self.plan):
+            s_x = calibrated_scale(x, self.bits) if self.scales is None else self.scales[i]
+            used.append(s_x)
+            qx = B.adapt_quantize_f32(x, s_x, self.bits)
+            acc = B.adapt_approx_conv_transpose2d(self.lut, qx, self.qws[i][0], s, p)
+            if keep is not None:
+                keep.append(acc)
+            n, c, h, w = acc.shape
+            y = B.adapt_dequant_i32(acc, _f(s_x) * _f(self.qws[i][1]), n, c, h * w)
+            x = B.adapt_tanh_f32(y, out=y) if i == nl - 1 else B.adapt_relu_f32(y, out=y)
+        if self.scales is None:
+            self.scales = used
+        return dict(out=x, scales=used, last_acc=acc)
+
+
+def lut_macs_resnet20(batch: int) -> int:
+    macs, hw = 0, 32
+    for cin, cout, s in resnet20_plan():
+        hw = hw // s
+        macs += cout * hw * hw * cin * 9
+    return batch * (macs + 64 * 10)
+
+
+def lut_macs_lstm(T, Bn, I, Hs) -> int:
+    return T * Bn * (I + Hs) * 4 * Hs
+
+
+def lut_macs_dcgan(batch: int, plan) -> int:
+    macs, hw = 0, 1
+    for i, (cin, cout, s, p) in enumerate(plan):
+        macs += hw * hw * cin * cout * 16
+        hw = (hw - 1) * s - 2 * p + 4
+    return batch * macs

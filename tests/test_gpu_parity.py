@@ -1,0 +1,362 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Integer results must be bit-exact; fp32 results within 1e-6 relative (they are in fact
+produced by the same sequence of IEEE operations, and the elementwise tests check bit equality,
+because one differing ulp before a quantiser would flip an integer downstream).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+from oracle import networks as onet
+from paper_2203_04071_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-6
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2203_04071_amd import binding
+    binding.load()
+    assert torch.cuda.is_available()
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def assert_f32_close(got, want):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    assert got.shape == want.shape
+    denom = np.maximum(np.abs(want), 1e-30)
+    bad = np.abs(got - want) > RTOL * denom
+    bad &= ~((got == 0) & (want == 0))
+    assert not bad.any(), f"{bad.sum()} of {bad.size} differ; max rel {np.max(np.abs(got - want) / denom)}"
+
+
+def bits_equal(a, b):
+    a, b = np.ascontiguousarray(a, np.float32), np.ascontiguousarray(b, np.float32)
+    return a.shape == b.shape and ((a.view(np.uint32) == b.view(np.uint32)) | ((a == 0) & (b == 0))).all()
+
+
+# ------------------------------------------------------------------ quantiser / dequantiser
+
+@pytest.mark.parametrize("bits", [2, 4, 6, 7, 8])
+@pytest.mark.parametrize("n", [0, 1, 15, 16, 17, 4099, 1 << 20])
+def test_quantize_bit_exact(B, bits, n):
+    rng = np.random.default_rng(bits * 1000 + n % 997)
+    x = (rng.standard_normal(n) * 3).astype(np.float32)
+    if n >= 15:
+        x[:7] = [np.nan, np.inf, -np.inf, 0.0, -0.0, 1e30, -1e30]
+        s0 = np.float32(0.37)
+        x[7:15] = np.array([0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 3.5, 4.5], np.float32) * s0   # ties
+    for s in (np.float32(0.37), orc.scale_from_amax(orc.absmax(x[np.isfinite(x)]) if n else 0.0, bits)):
+        got = host(B.adapt_quantize_f32(dev(x), s, bits)) if n else np.empty(0, np.int8)
+        assert (got == orc.quantize(x, s, bits)).all()
+
+
+def test_quantize_unaligned_pointers(B):
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal(1000).astype(np.float32)
+    xd = dev(x)
+    out = torch.zeros(1003, dtype=torch.int8, device="cuda")
+    B.adapt_quantize_f32(xd[1:], 0.05, 8, out=out[3:3 + 999])
+    assert (host(out)[3:3 + 999] == orc.quantize(x[1:], 0.05, 8)).all()
+    assert host(out)[:3].tolist() == [0, 0, 0] and host(out)[-1] == 0
+
+
+@pytest.mark.parametrize("n", [0, 1, 5, 1023, 1 << 18, (1 << 20) + 3])
+def test_absmax_exact(B, n):
+    rng = np.random.default_rng(n % 1000)
+    x = rng.standard_normal(n).astype(np.float32)
+    if n > 4:
+        x[3] = np.nan
+        x[n // 2] = -7.25
+    got = B.adapt_absmax_f32(dev(x)) if n else B.adapt_absmax_f32(torch.empty(0, device="cuda"))
+    assert host(got)[0] == orc.absmax(x)
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (5, 3, 7), (4, 16, 64), (64, 128, 1), (3, 10, 1), (2, 5, 12)])
+@pytest.mark.parametrize("with_bias", [False, True])
+def test_dequant_bit_exact(B, shape, with_bias):
+    rng = np.random.default_rng(sum(shape))
+    acc = rng.integers(-2**31, 2**31 - 1, size=shape, dtype=np.int64).astype(np.int32)
+    acc.reshape(-1)[0] = 2**24 + 1
+    bias = rng.standard_normal(shape[1]).astype(np.float32) if with_bias else None
+    s = np.float32(0.0123)
+    want = orc.dequant(acc, s, *shape, bias)
+    got = host(B.adapt_dequant_i32(dev(acc), s, *shape, dev(bias) if with_bias else None))
+    assert bits_equal(got, want)
+    assert_f32_close(got, want)
+
+
+# ------------------------------------------------------------------ fp32 glue
+
+def test_glue_ops_bit_exact(B):
+    rng = np.random.default_rng(77)
+    x = (rng.standard_normal((3, 5, 8, 8)) * 4).astype(np.float32)
+    y = (rng.standard_normal((3, 5, 8, 8)) * 4).astype(np.float32)
+    x[0, 0, 0, :3] = [np.nan, -0.0, 0.0]
+    assert bits_equal(host(B.adapt_relu_f32(dev(x))), orc.relu(x))
+    x[0, 0, 0, 0] = 1.0
+    assert bits_equal(host(B.adapt_add_f32(dev(x), dev(y))), orc.add(x, y))
+    assert bits_equal(host(B.adapt_add_f32(dev(x), dev(y), relu=True)), orc.relu(orc.add(x, y)))
+    assert bits_equal(host(B.adapt_avgpool_hw_f32(dev(x))), orc.avgpool_hw(x))
+    assert bits_equal(host(B.adapt_shortcut_a_f32(dev(x), 10)), orc.shortcut_a(x, 10))
+    odd = (rng.standard_normal((2, 3, 7, 5))).astype(np.float32)
+    assert bits_equal(host(B.adapt_shortcut_a_f32(dev(odd), 7)), orc.shortcut_a(odd, 7))
+    v = np.concatenate([np.linspace(-100, 100, 100001), rng.standard_normal(100000) * 3,
+                        [0.0, -0.0, 1e-30, -1e-30, 88.0, -87.0, 1e20]]).astype(np.float32)
+    assert bits_equal(host(B.adapt_tanh_f32(dev(v))), orc.tanh(v))
+    assert bits_equal(host(B.adapt_sigmoid_f32(dev(v))), orc.sigmoid(v))
+
+
+@pytest.mark.parametrize("Bn,Hs", [(1, 1), (3, 17), (64, 512)])
+def test_lstm_cell_bit_exact(B, Bn, Hs):
+    rng = np.random.default_rng(Bn + Hs)
+    a1 = rng.integers(-300000, 300000, size=(Bn, 4 * Hs)).astype(np.int32)
+    a2 = rng.integers(-300000, 300000, size=(Bn, 4 * Hs)).astype(np.int32)
+    bias = rng.standard_normal(4 * Hs).astype(np.float32)
+    c = rng.standard_normal((Bn, Hs)).astype(np.float32)
+    s1, s2 = np.float32(1.3e-5), np.float32(2.1e-5)
+    for b in (bias, None):
+        h_w, c_w = orc.lstm_cell(a1, a2, s1, s2, b, c)
+        cd = dev(c)
+        hd = torch.empty((Bn, Hs), dtype=torch.float32, device="cuda")
+        B.adapt_lstm_cell_f32(dev(a1), dev(a2), s1, s2, dev(b) if b is not None else None, cd, hd)
+        assert bits_equal(host(hd), h_w) and bits_equal(host(cd), c_w)
+
+
+# ------------------------------------------------------------------ table-lookup linear layer
+
+LINEAR_SHAPES = [
+    (1, 1, 1), (1, 7, 3), (3, 5, 17), (64, 256, 128), (65, 33, 9), (100, 64, 40), (130, 300, 24),
+    (1000, 17, 5), (1025, 72, 16), (2500, 40, 33), (64, 512, 200), (7, 1000, 70),
+]
+
+
+@pytest.mark.parametrize("bits", [2, 5, 6, 7, 8])
+@pytest.mark.parametrize("shape", LINEAR_SHAPES)
+def test_linear_bit_exact(B, bits, shape):
+    M, K, N = shape
+    rng = np.random.default_rng(bits * 100000 + M * 31 + K * 7 + N)
+    dist = "uniform" if (M + N) % 2 else "gauss"
+    A = wl.random_i8(rng, (M, K), bits, dist)
+    W = wl.random_i8(rng, (N, K), bits, dist)
+    n = 1 << bits
+    lut = rng.integers(-32768, 32768, size=(n, n)).astype(np.int32)     # arbitrary, asymmetric
+    L = B.Lut(lut, bits)
+    assert L.info()["storage"] == 0
+    got = host(B.adapt_approx_linear(L, dev(A), dev(W)))
+    assert (got == orc.approx_linear(lut, bits, A, W, threads=4)).all()
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_linear_wide_tables_and_wraparound(B, bits):
+    """Entries beyond int16 use the two-half image; sums wrap modulo 2^32 like the oracle's."""
+    rng = np.random.default_rng(bits)
+    n = 1 << bits
+    lut = rng.integers(-2**31, 2**31 - 1, size=(n, n), dtype=np.int64).astype(np.int32)
+    L = B.Lut(lut, bits)
+    assert L.info()["storage"] == 1 and L.info()["min"] == lut.min() and L.info()["max"] == lut.max()
+    for (M, K, N) in [(70, 130, 20), (1100, 40, 9), (5, 600, 3)]:
+        A = wl.random_i8(rng, (M, K), bits)
+        W = wl.random_i8(rng, (N, K), bits)
+        got = host(B.adapt_approx_linear(L, dev(A), dev(W)))
+        assert (got == orc.approx_linear(lut, bits, A, W, threads=4)).all()
+    x = wl.random_i8(rng, (2, 3, 6, 6), bits)
+    w = wl.random_i8(rng, (4, 3, 3, 3), bits)
+    assert (host(B.adapt_approx_conv2d(L, dev(x), dev(w), (1, 1), (1, 1))) == orc.approx_conv2d(lut, bits, x, w, (1, 1), (1, 1))).all()
+    wt = wl.random_i8(rng, (3, 2, 4, 4), bits)
+    assert (host(B.adapt_approx_conv_transpose2d(L, dev(x), dev(wt), 2, 1)) == orc.approx_conv_transpose2d(lut, bits, x, wt, 2, 1)).all()
+
+
+def test_linear_empty_and_degenerate(B):
+    lut = wl.make_lut(6)
+    L = B.Lut(lut, 6)
+    e = lambda *s: torch.empty(s, dtype=torch.int8, device="cuda")
+    assert B.adapt_approx_linear(L, e(0, 8), e(4, 8)).shape == (0, 4)
+    assert B.adapt_approx_linear(L, e(3, 8), e(0, 8)).shape == (3, 0)
+    out = torch.full((3, 4), 99, dtype=torch.int32, device="cuda")
+    B.adapt_approx_linear(L, e(3, 0), e(4, 0), out=out)          # K = 0: empty sums
+    assert (host(out) == 0).all()
+    # operands at both ends of the range, including -H which the quantiser itself never produces
+    A = np.array([[-32, 31, 0, -32]], dtype=np.int8)
+    W = np.array([[-32, -32, 31, 0], [31, 0, -32, -32]], dtype=np.int8)
+    assert (host(B.adapt_approx_linear(L, dev(A), dev(W))) == orc.approx_linear(lut, 6, A, W)).all()
+
+
+def test_linear_deterministic_and_overwrites(B):
+    c = wl.config1()
+    L = B.Lut(c["lut"], 8)
+    A, W = dev(c["A"]), dev(c["W"])
+    out = torch.full((64, 128), -1, dtype=torch.int32, device="cuda")
+    B.adapt_approx_linear(L, A, W, out=out)
+    first = host(out).copy()
+    B.adapt_approx_linear(L, A, W, out=out)
+    assert (host(out) == first).all()
+
+
+def test_errors_on_device_handles(B):
+    L = B.Lut(wl.make_lut(6), 6)
+    x = torch.zeros((1, 4, 5, 5), dtype=torch.int8, device="cuda")
+    w = torch.zeros((4, 2, 3, 3), dtype=torch.int8, device="cuda")
+    w1 = torch.zeros((4, 4, 7, 7), dtype=torch.int8, device="cuda")
+    dummy = torch.zeros((1, 4, 1, 1), dtype=torch.int32, device="cuda")
+    with pytest.raises(B.AdaptError) as e:
+        B.adapt_approx_conv2d(L, x, w1, out=dummy)           # filter larger than the input
+    assert e.value.code == -1
+    with pytest.raises(B.AdaptError) as e:
+        B.adapt_approx_conv2d(L, x, w, groups=2, out=dummy)
+    assert e.value.code == -2
+    with pytest.raises(B.AdaptError):
+        B.adapt_quantize_f32(torch.zeros(4, device="cuda"), -1.0, 8)
+
+
+# ------------------------------------------------------------------ convolutions
+
+CONV_CASES = [
+    # N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw
+    (2, 3, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, 1),
+    (1, 4, 9, 7, 6, 3, 3, 2, 2, 1, 1, 1, 1),
+    (2, 2, 6, 10, 3, 1, 1, 1, 1, 0, 0, 1, 1),
+    (1, 3, 7, 7, 2, 5, 3, 2, 1, 2, 0, 1, 1),
+    (1, 4, 8, 8, 8, 3, 3, 1, 1, 2, 2, 2, 2),
+    (1, 2, 4, 4, 3, 4, 4, 1, 1, 3, 3, 1, 1),
+    (3, 16, 32, 32, 16, 3, 3, 1, 1, 1, 1, 1, 1),     # several row tiles, N = one channel tile
+    (2, 16, 32, 32, 32, 3, 3, 2, 2, 1, 1, 1, 1),
+    (5, 7, 13, 11, 19, 3, 3, 1, 1, 1, 1, 1, 1),      # ragged everything
+    (1, 40, 6, 6, 70, 3, 3, 1, 1, 1, 1, 1, 1),       # short M, K split over waves
+]
+
+
+@pytest.mark.parametrize("bits", [6, 8])
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv2d_bit_exact(B, bits, case):
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw = case
+    rng = np.random.default_rng(bits + sum(case))
+    x = wl.random_i8(rng, (N, Cin, H, W), bits, "gauss")
+    w = wl.random_i8(rng, (Cout, Cin, kh, kw), bits, "gauss")
+    lut = wl.make_lut(bits)
+    L = B.Lut(lut, bits)
+    got = host(B.adapt_approx_conv2d(L, dev(x), dev(w), (sh, sw), (ph, pw), (dh, dw)))
+    want = orc.approx_conv2d(lut, bits, x, w, (sh, sw), (ph, pw), (dh, dw), threads=4)
+    assert got.shape == want.shape and (got == want).all()
+
+
+def test_conv2d_padding_is_looked_up(B):
+    c = 11
+    t = np.full((16, 16), c, dtype=np.int32)
+    rng = np.random.default_rng(5)
+    x = wl.random_i8(rng, (2, 4, 5, 6), 4)
+    w = wl.random_i8(rng, (3, 4, 3, 3), 4)
+    got = host(B.adapt_approx_conv2d(B.Lut(t, 4), dev(x), dev(w), (1, 1), (1, 1)))
+    assert (got == c * 4 * 9).all()
+
+
+CONVT_CASES = [
+    # N, Cin, H, W, Cout, k, stride, pad
+    (2, 3, 1, 1, 4, 4, 1, 0),
+    (1, 4, 4, 4, 3, 4, 2, 1),
+    (2, 2, 5, 3, 2, 3, 2, 0),
+    (1, 3, 3, 4, 2, 3, 1, 1),
+    (1, 2, 4, 4, 2, 5, 3, 2),
+    (3, 20, 8, 8, 12, 4, 2, 1),
+    (2, 9, 16, 16, 3, 4, 2, 1),
+    (70, 10, 1, 1, 24, 4, 1, 0),
+]
+
+
+@pytest.mark.parametrize("bits", [6, 8])
+@pytest.mark.parametrize("case", CONVT_CASES)
+def test_conv_transpose2d_bit_exact(B, bits, case):
+    N, Cin, H, W, Cout, k, s, p = case
+    rng = np.random.default_rng(bits + sum(case))
+    x = wl.random_i8(rng, (N, Cin, H, W), bits, "gauss")
+    w = wl.random_i8(rng, (Cin, Cout, k, k), bits, "gauss")
+    lut = wl.make_lut(bits)
+    got = host(B.adapt_approx_conv_transpose2d(B.Lut(lut, bits), dev(x), dev(w), s, p))
+    want = orc.approx_conv_transpose2d(lut, bits, x, w, s, p, threads=4)
+    assert got.shape == want.shape and (got == want).all()
+
+
+# ------------------------------------------------------------------ the five benchmark configurations
+
+def test_config1_linear(B):
+    c = wl.config1()
+    L = B.Lut(c["lut"], 8)
+    acc = B.adapt_approx_linear(L, dev(c["A"]), dev(c["W"]))
+    want = orc.approx_linear(c["lut"], 8, c["A"], c["W"])
+    assert (host(acc) == want).all()
+    y = B.adapt_dequant_i32(acc, c["scale"], 64, 128, 1)
+    assert_f32_close(host(y), orc.dequant(want, c["scale"], 64, 128, 1))
+
+
+def test_config2_conv_full_size(B):
+    c = wl.config2()
+    bits = 8
+    th = orc.host_threads()
+    x, w = dev(c["x"]), dev(c["w"])
+    s_x = np.float32(host(B.adapt_absmax_f32(x))[0]) / np.float32(127)
+    s_w = np.float32(host(B.adapt_absmax_f32(w))[0]) / np.float32(127)
+    assert s_x == orc.scale_from_amax(orc.absmax(c["x"]), bits) and s_w == orc.scale_from_amax(orc.absmax(c["w"]), bits)
+    qx, qw = B.adapt_quantize_f32(x, s_x, bits), B.adapt_quantize_f32(w, s_w, bits)
+    oqx, oqw = orc.quantize(c["x"], s_x, bits), orc.quantize(c["w"], s_w, bits)
+    assert (host(qx) == oqx).all() and (host(qw) == oqw).all()
+    L = B.Lut(c["lut"], bits)
+    acc = B.adapt_approx_conv2d(L, qx, qw, (1, 1), (1, 1))
+    want = orc.approx_conv2d(c["lut"], bits, oqx, oqw, (1, 1), (1, 1), threads=th)
+    assert (host(acc) == want).all()
+    y = B.adapt_dequant_i32(acc, np.float32(s_x) * np.float32(s_w), 32, 64, 1024)
+    assert_f32_close(host(y), orc.dequant(want, np.float32(s_x) * np.float32(s_w), 32, 64, 1024))
+
+
+def test_config3_resnet20_full_size(B):
+    from paper_2203_04071_amd import networks as gnet
+    c = wl.config3()
+    th = orc.host_threads()
+    want = onet.resnet20(c, threads=th, keep=True)
+    net = gnet.ResNet20(c)
+    keep = []
+    got = net.forward(dev(c["x"]), keep=keep)
+    assert [np.float32(s) for s in got["scales"]] == [np.float32(s) for s in want["scales"]]
+    for i, (g, o) in enumerate(zip(keep, want["trace"])):
+        assert (host(g) == o).all(), f"conv {i}"
+    assert (host(got["fc_acc"]) == want["fc_acc"]).all()
+    assert_f32_close(host(got["logits"]), want["logits"])
+    again = net.forward(dev(c["x"]))                       # frozen scales, no host reads
+    assert (host(again["fc_acc"]) == want["fc_acc"]).all()
+
+
+def test_config4_lstm_full_size(B):
+    from paper_2203_04071_amd import networks as gnet
+    c = wl.config4()
+    th = orc.host_threads()
+    want = onet.lstm(c, threads=th)
+    got = gnet.LSTM(c).forward(dev(c["x"]))
+    assert np.float32(got["s_x"]) == np.float32(want["s_x"])
+    assert (host(got["acc_ih"]) == want["acc_ih"]).all()
+    assert (host(got["acc_hh_last"]) == want["acc_hh_last"]).all()
+    assert_f32_close(host(got["hs"]), want["hs"])
+    assert_f32_close(host(got["c"]), want["c"])
+
+
+@pytest.mark.parametrize("bits", [6, 8])
+def test_config5_dcgan_full_size(B, bits):
+    from paper_2203_04071_amd import networks as gnet
+    c = wl.config5(bits=bits)
+    th = orc.host_threads()
+    want = onet.dcgan(c, threads=th, keep=True)
+    keep = []
+    got = gnet.DCGAN(c).forward(dev(c["z"]), keep=keep)
+    assert [np.float32(s) for s in got["scales"]] == [np.float32(s) for s in want["scales"]]
+    for i, (g, o) in enumerate(zip(keep, want["accs"])):
+        assert (host(g) == o).all(), f"layer {i}"
+    assert_f32_close(host(got["out"]), want["out"])
