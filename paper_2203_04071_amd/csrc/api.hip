@@ -10,6 +10,7 @@
 
 #include "../../include/adapt_mi355.h"
 #include "elementwise.hpp"
+#include "lut_lines.hpp"
 #include "lut_rows.hpp"
 
 namespace {
@@ -51,6 +52,16 @@ struct adapt_lut {
     int rs;                 // entries per image row = 2^b + 2
     int img_bytes;          // per image, multiple of 16
     uint16_t *img_dev[2];   // [0] = only / low half, [1] = high half
+    uint16_t *lut16_dev[2]; // same halves, plain [a & mask][w & mask] order (source of the derived line tables)
+};
+
+struct adapt_weights {
+    int kind;               // 0 linear, 1 conv2d
+    int bits, storage, device;
+    int N, Cin, kh, kw;     // linear: Cin = K, kh = kw = 1
+    int Cp, Cc, n_tiles;    // padded inner length (multiple of 8; linear: of 32), steps per tap, 8-channel tiles
+    size_t dt_bytes;        // per table-half
+    uint4 *dt_dev[2];
 };
 
 extern "C" {
@@ -85,6 +96,7 @@ int adapt_lut_create(adapt_lut **out, int bits, const int32_t *table_host) {
     l->rs = n + 2;
     l->img_bytes = ((n * l->rs * 2 + 15) / 16) * 16;
     l->img_dev[0] = l->img_dev[1] = nullptr;
+    l->lut16_dev[0] = l->lut16_dev[1] = nullptr;
     if (hipGetDevice(&l->device) != hipSuccess) {
         delete l;
         return fail(ADAPT_ERR_HIP, "adapt_lut_create: hipGetDevice failed");
@@ -102,9 +114,19 @@ int adapt_lut_create(adapt_lut **out, int bits, const int32_t *table_host) {
             }
         hipError_t e = hipMalloc((void **)&l->img_dev[half], (size_t)l->img_bytes);
         if (e == hipSuccess) e = hipMemcpy(l->img_dev[half], img.data(), (size_t)l->img_bytes, hipMemcpyHostToDevice);
+        // plain copy indexed by the two's-complement wrap of the operands: [a & mask][w & mask]
+        std::vector<uint16_t> plain((size_t)n * n);
+        const int hh = n >> 1;
+        for (int a = -hh; a < hh; ++a)
+            for (int w = -hh; w < hh; ++w)
+                plain[(size_t)(a & (n - 1)) * n + (w & (n - 1))] = img[(size_t)(w + hh) * l->rs + (a + hh)];
+        if (e == hipSuccess) e = hipMalloc((void **)&l->lut16_dev[half], plain.size() * 2);
+        if (e == hipSuccess) e = hipMemcpy(l->lut16_dev[half], plain.data(), plain.size() * 2, hipMemcpyHostToDevice);
         if (e != hipSuccess) {
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 2; ++j) {
                 if (l->img_dev[j]) (void)hipFree(l->img_dev[j]);
+                if (l->lut16_dev[j]) (void)hipFree(l->lut16_dev[j]);
+            }
             delete l;
             return fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP,
                         "adapt_lut_create: device image: %s", hipGetErrorString(e));
@@ -116,8 +138,10 @@ int adapt_lut_create(adapt_lut **out, int bits, const int32_t *table_host) {
 
 int adapt_lut_destroy(adapt_lut *lut) {
     if (!lut) return ADAPT_OK;
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 2; ++j) {
         if (lut->img_dev[j]) (void)hipFree(lut->img_dev[j]);
+        if (lut->lut16_dev[j]) (void)hipFree(lut->lut16_dev[j]);
+    }
     delete lut;
     return ADAPT_OK;
 }
@@ -253,6 +277,177 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     return rc;
 }
 
+
+/* ---- "lines" path: derived tables streamed through LDS (long matrices) ---- */
+
+template <int R, bool SIGNED, bool REGULAR>
+int launch_lines_inst(const adapt::LinesParams &p, unsigned grid, hipStream_t s) {
+    adapt::lut_lines_kernel<R, SIGNED, REGULAR><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+template <int R, bool SIGNED, bool REGULAR>
+int launch_lines_fast(const adapt::LinesParams &p, unsigned grid, hipStream_t s) {
+    if (p.bits == 8) adapt::lut_lines_fast_kernel<R, SIGNED, REGULAR, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    else adapt::lut_lines_fast_kernel<R, SIGNED, REGULAR, false><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+template <int R>
+int launch_lines_r(const adapt::LinesParams &p, unsigned grid, bool sgn, bool regular, hipStream_t s) {
+    if (p.Cc % 4 == 0) {       // groups of four steps never straddle a filter tap: fully unrolled variant
+        if (regular) return sgn ? launch_lines_fast<R, true, true>(p, grid, s) : launch_lines_fast<R, false, true>(p, grid, s);
+        return sgn ? launch_lines_fast<R, true, false>(p, grid, s) : launch_lines_fast<R, false, false>(p, grid, s);
+    }
+    if (regular) return sgn ? launch_lines_inst<R, true, true>(p, grid, s) : launch_lines_inst<R, false, true>(p, grid, s);
+    return sgn ? launch_lines_inst<R, true, false>(p, grid, s) : launch_lines_inst<R, false, false>(p, grid, s);
+}
+
+struct LinesShape {
+    int kind;            // 0 linear, 1 conv2d
+    int N, Cin, kh, kw;  // output channels, inner length per tap, taps
+    int Cp, Cc, n_tiles;
+    size_t dt_bytes;     // per table half
+};
+
+LinesShape lines_shape(int kind, int bits, int N, int Cin, int kh, int kw) {
+    LinesShape q;
+    q.kind = kind; q.N = N; q.Cin = Cin; q.kh = kh; q.kw = kw;
+    q.Cp = kind == 0 ? ((Cin + 31) / 32) * 32 : ((Cin + 7) / 8) * 8;
+    q.Cc = q.Cp / 8;
+    q.n_tiles = (N + 7) / 8;
+    q.dt_bytes = (size_t)q.n_tiles * kh * kw * q.Cc * ((size_t)adapt::LINE_BYTES << bits);
+    return q;
+}
+
+int pack_lines(const adapt_lut *lut, const int8_t *w, const LinesShape &q, uint4 *const dt[2], hipStream_t s) {
+    for (int half = 0; half <= lut->storage; ++half) {
+        const size_t total = q.dt_bytes / 16;
+        size_t blocks = (total + 255) / 256;
+        if (blocks > 65536) blocks = 65536;
+        adapt::pack_line_tables_kernel<<<(unsigned)blocks, 256, 0, s>>>(lut->lut16_dev[half], w, dt[half], lut->bits, q.N, q.Cin,
+                                                                       q.kh * q.kw, q.Cc, q.n_tiles, 0);
+        HIP_TRY(hipGetLastError());
+    }
+    return ADAPT_OK;
+}
+
+struct LinesCall {       // per-call geometry of the activation side
+    int M, HoWo, Wo;
+    long long img_stride;
+    int oy_stride, ox_stride, ky_stride, kx_stride;
+};
+
+int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *xt, const LinesCall &c,
+              int32_t *out, hipStream_t s) {
+    int cu = 256;
+    {
+        int dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
+    }
+    // rows per lane: as many as still give every compute unit a workgroup
+    int R = 8;
+    auto wgs = [&](int r) { return (long long)((c.M + 128 * r - 1) / (128 * r)) * q.n_tiles; };
+    while (R > 2 && wgs(R) < cu) R /= 2;
+    adapt::LinesParams p;
+    p.xt = xt; p.out = out;
+    p.M = c.M; p.N = q.N; p.n_tiles = q.n_tiles;
+    p.Cc = q.Cc; p.taps = q.kh * q.kw; p.kw = q.kw; p.bits = bits;
+    p.HoWo = c.HoWo; p.Wo = c.Wo; p.img_stride = c.img_stride;
+    p.oy_stride = c.oy_stride; p.ox_stride = c.ox_stride; p.ky_stride = c.ky_stride; p.kx_stride = c.kx_stride;
+    const long long grid = wgs(R);
+    if (grid > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "lines path: grid too large");
+    // one base offset per lane is enough when the R rows of a lane are equally spaced in xt
+    const bool regular = (c.M % R == 0) && (c.HoWo == 1 || c.Wo % R == 0);
+    int rc = ADAPT_OK;
+    for (int half = 0; half <= storage && rc == ADAPT_OK; ++half) {
+        p.dt = dt[half];
+        p.shift = half == 0 ? -1 : 16;
+        const bool sgn = storage == 0 || half == 1;
+        if (R == 8) rc = launch_lines_r<8>(p, (unsigned)grid, sgn, regular, s);
+        else if (R == 4) rc = launch_lines_r<4>(p, (unsigned)grid, sgn, regular, s);
+        else rc = launch_lines_r<2>(p, (unsigned)grid, sgn, regular, s);
+    }
+    return rc;
+}
+
+// activation side of a linear layer: A itself when its rows are a multiple of 32 bytes, else a zero-padded copy
+int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *a, int32_t *out, int M, hipStream_t s) {
+    const int K = q.Cin, Kp = q.Cp;
+    int8_t *tmp = nullptr;
+    const int8_t *xt = a;
+    if (Kp != K) {
+        HIP_TRY(hipMallocAsync((void **)&tmp, (size_t)M * Kp + 16, s));
+        const size_t total = (size_t)M * Kp;
+        size_t blocks = (total + 255) / 256;
+        if (blocks > 65536) blocks = 65536;
+        adapt::pad_rows_kernel<<<(unsigned)blocks, 256, 0, s>>>(a, tmp, M, K, Kp);
+        xt = tmp;
+    }
+    LinesCall c;
+    c.M = M; c.HoWo = 1; c.Wo = 1; c.img_stride = Kp;
+    c.oy_stride = c.ox_stride = c.ky_stride = c.kx_stride = 0;
+    int rc = run_lines(bits, storage, q, dt, xt, c, out, s);
+    if (tmp) {
+        hipError_t fe = hipFreeAsync(tmp, s);
+        if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
+    }
+    return rc;
+}
+
+// activation side of a convolution: zero-padded channel-last copy of x
+int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *x, int32_t *out, int N, int H,
+                 int W, int Ho, int Wo, int sh, int sw, int ph, int pw, int dh, int dw, hipStream_t s) {
+    const int Hp = H + 2 * ph, Wp = W + 2 * pw, Cp = q.Cp;
+    const size_t xt_bytes = (size_t)N * Hp * Wp * Cp;
+    int8_t *xt = nullptr;
+    HIP_TRY(hipMallocAsync((void **)&xt, xt_bytes + 16, s));
+    {
+        const size_t total = xt_bytes / 4;
+        size_t blocks = (total + 255) / 256;
+        if (blocks > 65536) blocks = 65536;
+        adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(x, xt, N, q.Cin, H, W, ph, pw, Cp);
+    }
+    LinesCall c;
+    c.M = N * Ho * Wo; c.HoWo = Ho * Wo; c.Wo = Wo;
+    c.img_stride = (long long)Hp * Wp * Cp;
+    c.oy_stride = sh * Wp * Cp; c.ox_stride = sw * Cp; c.ky_stride = dh * Wp * Cp; c.kx_stride = dw * Cp;
+    int rc = run_lines(bits, storage, q, dt, xt, c, out, s);
+    hipError_t fe = hipFreeAsync(xt, s);
+    if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
+    return rc;
+}
+
+// limits of the lines path: 32-bit byte offsets into the activation copy, and a sane table stream
+bool lines_fits(long long xt_bytes, size_t dt_bytes, int storage) {
+    return xt_bytes < 0x7fffff00LL && dt_bytes * (size_t)(storage + 1) <= ((size_t)4 << 30);
+}
+
+// one-shot use: pack into a stream-ordered temporary, run, release
+template <typename F>
+int with_temp_tables(const adapt_lut *lut, const int8_t *w, const LinesShape &q, hipStream_t s, F &&body) {
+    uint4 *dt[2] = {nullptr, nullptr};
+    int rc = ADAPT_OK;
+    for (int half = 0; half <= lut->storage; ++half) {
+        hipError_t e = hipMallocAsync((void **)&dt[half], q.dt_bytes, s);
+        if (e != hipSuccess) {
+            rc = fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "hipMallocAsync(tables): %s", hipGetErrorString(e));
+            break;
+        }
+    }
+    if (rc == ADAPT_OK) rc = pack_lines(lut, w, q, dt, s);
+    if (rc == ADAPT_OK) rc = body(dt);
+    for (int half = 0; half < 2; ++half)
+        if (dt[half]) (void)hipFreeAsync(dt[half], s);
+    return rc;
+}
+
+// The lines path pays K*N*2^b table entries of packing and streams them once per 128*R rows:
+// worth it from a few thousand rows on.
+constexpr int LINES_MIN_ROWS = 4096;
+
 int check_lut(const adapt_lut *lut, const char *who) {
     if (!lut) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: lut is NULL", who);
     int dev = -1;
@@ -278,6 +473,13 @@ int adapt_approx_linear(const adapt_lut *lut, const int8_t *a_dev, const int8_t 
     g.mode = adapt::MODE_GEMM; g.M = M; g.N = N; g.Cin = K; g.taps = 1; g.kw = 1;
     g.H = 1; g.W = 1; g.Wo = 1; g.HoWo = 1; g.sh = g.sw = g.dh = g.dw = 1; g.ph = g.pw = 0;
     g.kstride = 1; g.img_stride = K;
+    if (M >= LINES_MIN_ROWS && K >= 8) {
+        const LinesShape q = lines_shape(0, lut->bits, N, K, 1, 1);
+        if (lines_fits((long long)M * q.Cp, q.dt_bytes, lut->storage))
+            return with_temp_tables(lut, w_dev, q, (hipStream_t)stream, [&](uint4 *const dt[2]) {
+                return lines_linear(lut->bits, lut->storage, q, dt, a_dev, acc_dev, M, (hipStream_t)stream);
+            });
+    }
     return run_rows(lut, a_dev, w_dev, acc_dev, g, (hipStream_t)stream);
 }
 
@@ -305,6 +507,15 @@ int adapt_approx_conv2d(const adapt_lut *lut, const int8_t *x_dev, const int8_t 
     g.H = H; g.W = W; g.Wo = (int)Wo; g.HoWo = (int)(Ho * Wo);
     g.sh = stride_h; g.sw = stride_w; g.ph = pad_h; g.pw = pad_w; g.dh = dil_h; g.dw = dil_w;
     g.kstride = H * W; g.img_stride = Cin * H * W;
+    if (g.M >= LINES_MIN_ROWS && Cin >= 4) {
+        const LinesShape q = lines_shape(1, lut->bits, Cout, Cin, kh, kw);
+        const long long xt_bytes = (long long)N * (H + 2LL * pad_h) * (W + 2LL * pad_w) * q.Cp;
+        if (lines_fits(xt_bytes, q.dt_bytes, lut->storage))
+            return with_temp_tables(lut, w_dev, q, (hipStream_t)stream, [&](uint4 *const dt[2]) {
+                return lines_conv2d(lut->bits, lut->storage, q, dt, x_dev, acc_dev, N, H, W, (int)Ho, (int)Wo, stride_h, stride_w,
+                                    pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream);
+            });
+    }
     return run_rows(lut, x_dev, w_dev, acc_dev, g, (hipStream_t)stream);
 }
 
@@ -328,6 +539,111 @@ int adapt_approx_conv_transpose2d(const adapt_lut *lut, const int8_t *x_dev, con
     g.sh = stride; g.sw = stride; g.ph = pad; g.pw = pad; g.dh = g.dw = 1;
     g.kstride = H * W; g.img_stride = Cin * H * W;
     return run_rows(lut, x_dev, w_dev, acc_dev, g, (hipStream_t)stream);
+}
+
+
+/* ------------------------------------------------------------------ pre-packed weights */
+
+static int weights_pack(adapt_weights **out, const adapt_lut *lut, const int8_t *w_dev, int kind, int N, int Cin, int kh,
+                        int kw, void *stream, const char *who) {
+    if (!out) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: out is NULL", who);
+    *out = nullptr;
+    int rc = check_lut(lut, who);
+    if (rc) return rc;
+    if (N < 1 || Cin < 1 || kh < 1 || kw < 1) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
+    if (!w_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: w_dev is NULL", who);
+    if ((long long)N * Cin * kh * kw > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "%s: more than 2^31-1 weights", who);
+    const LinesShape q = lines_shape(kind, lut->bits, N, Cin, kh, kw);
+    if (q.dt_bytes * (size_t)(lut->storage + 1) > ((size_t)64 << 30))
+        return fail(ADAPT_ERR_OUT_OF_MEMORY, "%s: packed tables would need %zu bytes", who, q.dt_bytes * (size_t)(lut->storage + 1));
+    adapt_weights *h = new (std::nothrow) adapt_weights();
+    if (!h) return fail(ADAPT_ERR_OUT_OF_MEMORY, "%s: host allocation failed", who);
+    h->kind = kind; h->bits = lut->bits; h->storage = lut->storage; h->device = lut->device;
+    h->N = N; h->Cin = Cin; h->kh = kh; h->kw = kw; h->Cp = q.Cp; h->Cc = q.Cc; h->n_tiles = q.n_tiles;
+    h->dt_bytes = q.dt_bytes;
+    h->dt_dev[0] = h->dt_dev[1] = nullptr;
+    for (int half = 0; half <= lut->storage; ++half) {
+        hipError_t e = hipMalloc((void **)&h->dt_dev[half], q.dt_bytes);
+        if (e != hipSuccess) {
+            for (int j = 0; j < 2; ++j)
+                if (h->dt_dev[j]) (void)hipFree(h->dt_dev[j]);
+            delete h;
+            return fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "%s: hipMalloc(%zu): %s", who, q.dt_bytes,
+                        hipGetErrorString(e));
+        }
+    }
+    rc = pack_lines(lut, w_dev, q, h->dt_dev, (hipStream_t)stream);
+    if (rc != ADAPT_OK) {
+        for (int j = 0; j < 2; ++j)
+            if (h->dt_dev[j]) (void)hipFree(h->dt_dev[j]);
+        delete h;
+        return rc;
+    }
+    *out = h;
+    return ADAPT_OK;
+}
+
+static LinesShape shape_of(const adapt_weights *h) {
+    LinesShape q;
+    q.kind = h->kind; q.N = h->N; q.Cin = h->Cin; q.kh = h->kh; q.kw = h->kw;
+    q.Cp = h->Cp; q.Cc = h->Cc; q.n_tiles = h->n_tiles; q.dt_bytes = h->dt_bytes;
+    return q;
+}
+
+static int check_weights(const adapt_weights *h, int kind, const char *who) {
+    if (!h) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: weights handle is NULL", who);
+    if (h->kind != kind) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: handle was packed for the other layer type", who);
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != h->device)
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: handle belongs to device %d, current device is %d", who, h->device, dev);
+    return ADAPT_OK;
+}
+
+int adapt_weights_pack_linear(adapt_weights **out, const adapt_lut *lut, const int8_t *w_dev, int K, int N, void *stream) {
+    return weights_pack(out, lut, w_dev, 0, N, K, 1, 1, stream, "adapt_weights_pack_linear");
+}
+
+int adapt_weights_pack_conv2d(adapt_weights **out, const adapt_lut *lut, const int8_t *w_dev, int Cout, int Cin, int kh, int kw,
+                              void *stream) {
+    return weights_pack(out, lut, w_dev, 1, Cout, Cin, kh, kw, stream, "adapt_weights_pack_conv2d");
+}
+
+int adapt_weights_destroy(adapt_weights *h) {
+    if (!h) return ADAPT_OK;
+    for (int j = 0; j < 2; ++j)
+        if (h->dt_dev[j]) (void)hipFree(h->dt_dev[j]);
+    delete h;
+    return ADAPT_OK;
+}
+
+int adapt_approx_linear_packed(const adapt_weights *h, const int8_t *a_dev, int32_t *acc_dev, int M, void *stream) {
+    int rc = check_weights(h, 0, "adapt_approx_linear_packed");
+    if (rc) return rc;
+    if (M < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_linear_packed: negative M");
+    if (M == 0) return ADAPT_OK;
+    if (!a_dev || !acc_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_linear_packed: NULL pointer");
+    if ((long long)M * h->Cp >= 0x7fffff00LL || (long long)M * h->N > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "adapt_approx_linear_packed: tensor with more than 2^31-1 elements");
+    return lines_linear(h->bits, h->storage, shape_of(h), h->dt_dev, a_dev, acc_dev, M, (hipStream_t)stream);
+}
+
+int adapt_approx_conv2d_packed(const adapt_weights *h, const int8_t *x_dev, int32_t *acc_dev, int N, int H, int W, int stride_h,
+                               int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, void *stream) {
+    int rc = check_weights(h, 1, "adapt_approx_conv2d_packed");
+    if (rc) return rc;
+    if (N < 0 || H < 1 || W < 1 || stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0 || dil_h < 1 || dil_w < 1)
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_conv2d_packed: bad dimension");
+    const long long eh = (long long)H + 2LL * pad_h - (long long)dil_h * (h->kh - 1) - 1;
+    const long long ew = (long long)W + 2LL * pad_w - (long long)dil_w * (h->kw - 1) - 1;
+    if (eh < 0 || ew < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_conv2d_packed: filter larger than padded input");
+    const long long Ho = eh / stride_h + 1, Wo = ew / stride_w + 1;
+    if (N == 0) return ADAPT_OK;
+    if (!x_dev || !acc_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_conv2d_packed: NULL pointer");
+    const long long xt_bytes = (long long)N * (H + 2LL * pad_h) * (W + 2LL * pad_w) * h->Cp;
+    if (xt_bytes >= 0x7fffff00LL || (long long)N * h->N * Ho * Wo > 0x7fffffffLL || (long long)N * Ho * Wo > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "adapt_approx_conv2d_packed: tensor with more than 2^31-1 elements");
+    return lines_conv2d(h->bits, h->storage, shape_of(h), h->dt_dev, x_dev, acc_dev, N, H, W, (int)Ho, (int)Wo, stride_h, stride_w,
+                        pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream);
 }
 
 /* ------------------------------------------------------------------ fp32 operations between layers */

@@ -1,0 +1,627 @@
+// "Lines" kernel: table-lookup matrix product for long matrices (many rows per weight).
+//
+// Idea (gfx950): a 16-bit LDS gather delivers one table entry per lane per bank cycle and suffers
+// bank conflicts that depend on the activation statistics.  Because the weights of a layer are
+// static, the entries a workgroup needs at inner step k, for its 8 output channels n and ALL
+// activation values a, form a small derived table  D_k[a][n] = T[a][W[n][k]]  (Sec. III-C: the
+// table is a 1:1 image of the multiplier, so re-ordering it changes nothing).  Stored activation-
+// major, one lookup with the activation as line index returns the entries of 8 output channels in
+// one 128-bit LDS read.  Eight inner steps (one per lane of an 8-lane group, "k-sub" j) share a
+// 128-byte line, so the 8 lanes that serve one matrix row read 8 different 16-byte columns: reads
+// are conflict-free by construction whatever the activations are.
+//
+// Derived tables are built once per layer by pack_line_tables_kernel (K*N*2^b entries) and
+// streamed from L2 into a double-buffered LDS slot, one 2^b x 128 B table per step; a workgroup
+// reuses each table for 128*R matrix rows.  Work per multiply-accumulate in the hot loop:
+// 1/8 LDS read + 1 v_dot2 (unpack one 16-bit half and add) + 1/4 address op.
+//
+// Mapping: workgroup = 1024 lanes = 128 row slots x 8 k-subs; lane (rs, j) owns rows rs*R .. rs*R+R-1
+// of the tile and inner indices ci in [j*Cc, (j+1)*Cc) of every filter tap; it keeps 8*R partial
+// sums which are reduced over j at the end.  Activations come from a channel-last, zero-padded
+// copy of the input (conv) or from the row-major activation matrix (linear), so the address of a
+// lane's next activations is base_row + tap_offset + j*Cc + t with no bounds logic; a padded tap
+// reads activation 0 and therefore adds T[0][w], as the definition of the layer demands.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+namespace adapt {
+
+constexpr int LINES_THREADS = 1024;
+constexpr int LINE_BYTES = 128;      // 8 k-subs x 8 channels x int16
+
+typedef short short2_t __attribute__((ext_vector_type(2)));
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+struct LinesParams {
+    const int8_t *xt;       // activations (see above)
+    const uint4 *dt;        // derived tables [n_tiles][steps][2^b lines][8 columns] x 16 B
+    int32_t *out;
+    int M, N, n_tiles;
+    int Cc, taps, kw;       // steps = taps * Cc
+    int bits;
+    int HoWo, Wo;           // linear: 1, 1
+    long long img_stride;   // bytes of xt per image (linear: bytes per row); the whole of xt is < 2^31 bytes
+    int oy_stride, ox_stride;   // bytes of xt per output row / column step (stride * padded width * Cp, stride * Cp)
+    int ky_stride, kx_stride;   // bytes of xt per filter row / column (dilation * padded width * Cp, dilation * Cp)
+    int shift;              // < 0: out = acc; >= 0: out += acc << shift
+};
+
+// NCHW int8 -> zero-padded channel-last copy [N][H + 2 ph][W + 2 pw][Cp], Cp a multiple of 8
+__global__ void pad_channels_last_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ xt, int N, int C, int H,
+                                         int W, int ph, int pw, int Cp) {
+    const int Hp = H + 2 * ph, Wp = W + 2 * pw;
+    const size_t total = (size_t)N * Hp * Wp * (Cp / 4);
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        // consecutive threads walk along x for a fixed group of 4 channels: reads coalesce per channel plane
+        const int xp = (int)(i % Wp);
+        size_t r = i / Wp;
+        const int c4 = (int)(r % (Cp / 4));
+        r /= (Cp / 4);
+        const int yp = (int)(r % Hp);
+        const int n = (int)(r / Hp);
+        const int y = yp - ph, xx = xp - pw;
+        uint32_t v = 0;
+        if (y >= 0 && y < H && xx >= 0 && xx < W) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c = c4 * 4 + q;
+                if (c < C) v |= (uint32_t)(uint8_t)x[(((size_t)n * C + c) * H + y) * W + xx] << (8 * q);
+            }
+        }
+        *reinterpret_cast<uint32_t *>(xt + (((size_t)n * Hp + yp) * Wp + xp) * Cp + c4 * 4) = v;
+    }
+}
+
+// [M][K] int8 -> [M][Kp] with zero fill, Kp a multiple of 32
+__global__ void pad_rows_kernel(const int8_t *__restrict__ a, int8_t *__restrict__ at, int M, int K, int Kp) {
+    const size_t total = (size_t)M * Kp;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int k = (int)(i % Kp);
+        const size_t m = i / Kp;
+        at[i] = k < K ? a[m * K + k] : (int8_t)0;
+    }
+}
+
+// Derived tables.  lut16: [2^b][2^b] 16-bit entries, index [a & mask][w & mask] (two's-complement
+// wrap of the signed operands, so activation 0 is line 0).  One thread writes the 8 channel entries
+// of (n-tile, step, line a, k-sub j).  wmode 0: w[n][K] / [Cout][Cin][taps]; wmode 1: [Cin][Cout][taps].
+__global__ void pack_line_tables_kernel(const uint16_t *__restrict__ lut16, const int8_t *__restrict__ w,
+                                        uint4 *__restrict__ dt, int bits, int N, int Cin, int taps, int Cc,
+                                        int n_tiles, int wmode) {
+    const int lines = 1 << bits, mask = lines - 1;
+    const size_t per_table = (size_t)lines * 8;
+    const size_t steps = (size_t)taps * Cc;
+    const size_t total = (size_t)n_tiles * steps * per_table;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int j = (int)(i & 7);
+        const int a = (int)((i >> 3) & mask);
+        const size_t ts = i / per_table;
+        const int step = (int)(ts % steps);
+        const int nt = (int)(ts / steps);
+        const int tap = step / Cc, t = step - tap * Cc;
+        const int ci = j * Cc + t;
+        uint32_t e[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const int n = nt * 8 + c;
+            uint32_t v = 0;
+            if (n < N && ci < Cin) {
+                const size_t wi = wmode == 0 ? ((size_t)n * Cin + ci) * taps + tap : ((size_t)ci * N + n) * taps + tap;
+                v = lut16[(size_t)a * lines + ((int)w[wi] & mask)];
+            }
+            e[c] = v;
+        }
+        dt[i] = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+    }
+}
+
+template <bool SIGNED>
+__device__ __forceinline__ void accum8(uint32_t *acc, const uint4 v) {
+    const uint32_t r[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (SIGNED) {
+            const short2_t s = __builtin_bit_cast(short2_t, r[q]);
+            acc[2 * q] = (uint32_t)__builtin_amdgcn_sdot2(s, short2_t{1, 0}, (int)acc[2 * q], false);
+            acc[2 * q + 1] = (uint32_t)__builtin_amdgcn_sdot2(s, short2_t{0, 1}, (int)acc[2 * q + 1], false);
+        } else {
+            const ushort2_t s = __builtin_bit_cast(ushort2_t, r[q]);
+            acc[2 * q] = __builtin_amdgcn_udot2(s, ushort2_t{1, 0}, acc[2 * q], false);
+            acc[2 * q + 1] = __builtin_amdgcn_udot2(s, ushort2_t{0, 1}, acc[2 * q + 1], false);
+        }
+    }
+}
+
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+typedef const __attribute__((address_space(1))) void *global_void_ptr;
+
+constexpr int TABLE_U4_MAX = 256 * 8;    // 16-byte units of one 8-bit table (32 KB)
+
+// s_waitcnt immediates below use the gfx9 encoding: vmcnt in bits 3:0, expcnt (left at 7) in 6:4, lgkmcnt(0) in 11:8
+
+// Asynchronous copy of one derived table (table_u4 16-byte units) from global memory straight into
+// an LDS buffer (no registers in between): lane l of a wave writes the 16 bytes at M0 + 16 l.
+// Written in assembly so that the compiler neither counts these operations nor guards later LDS
+// reads against them; the kernel orders them itself with wait_and_barrier().
+__device__ __forceinline__ void table_dma(const uint4 *src, uint4 *dst, int table_u4, int wave, int lane) {
+    const int u0 = wave * 64;
+    if (u0 < table_u4) {
+        if (u0 + lane < table_u4) {
+            const uint32_t lds_addr = (uint32_t)(uintptr_t)(lds_void_ptr)(dst + u0);
+            const uint32_t voff = (uint32_t)(u0 + lane) * 16u;
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                         :
+                         : "v"(voff), "s"(src), "s"(lds_addr)
+                         : "memory", "m0");
+        }
+    }
+    const int u1 = u0 + LINES_THREADS;
+    if (u1 < table_u4) {
+        const uint32_t lds_addr = (uint32_t)(uintptr_t)(lds_void_ptr)(dst + u1);
+        const uint32_t voff = (uint32_t)(u1 + lane) * 16u;
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :
+                     : "v"(voff), "s"(src), "s"(lds_addr)
+                     : "memory", "m0");
+    }
+}
+
+// wait until at most `keep` of this wave's most recent memory operations are outstanding (memory
+// operations of one wave complete in order), and all of its LDS reads have returned
+__device__ __forceinline__ void wait_vm(int keep) {
+    switch (keep < 0 ? 0 : (keep > 10 ? 10 : keep)) {      // rounding down only waits longer
+        case 0: __builtin_amdgcn_s_waitcnt(0x0070); break;
+        case 1: __builtin_amdgcn_s_waitcnt(0x0071); break;
+        case 2: __builtin_amdgcn_s_waitcnt(0x0072); break;
+        case 3: __builtin_amdgcn_s_waitcnt(0x0073); break;
+        case 4: __builtin_amdgcn_s_waitcnt(0x0074); break;
+        case 5: __builtin_amdgcn_s_waitcnt(0x0075); break;
+        case 6: __builtin_amdgcn_s_waitcnt(0x0076); break;
+        case 7: __builtin_amdgcn_s_waitcnt(0x0077); break;
+        case 8: __builtin_amdgcn_s_waitcnt(0x0078); break;
+        case 9: __builtin_amdgcn_s_waitcnt(0x0079); break;
+        default: __builtin_amdgcn_s_waitcnt(0x007a); break;
+    }
+}
+
+template <bool SIGNED>
+__device__ __forceinline__ void accum8(uint32_t *acc, const u32x4_t v) {
+    accum8<SIGNED>(acc, make_uint4(v.x, v.y, v.z, v.w));
+}
+
+// R: rows per lane.  SIGNED: entries are int16 (else uint16 low halves of a wide table).
+// REGULAR: the R rows of every lane are equally spaced in xt (linear layers; convolutions whose
+// output width is a multiple of R), so one base offset per lane suffices.
+template <int R, bool SIGNED, bool REGULAR>
+__global__ __launch_bounds__(LINES_THREADS) void lut_lines_kernel(const LinesParams p) {
+    // three table buffers: read one, the next one is complete, the third is being filled
+    __shared__ uint4 tbl[3 * TABLE_U4_MAX];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int j = tid & 7;
+    const int rs = tid >> 3;
+    const int nt = blockIdx.x % p.n_tiles;      // consecutive workgroup ids land on different XCDs:
+    const int mt = blockIdx.x / p.n_tiles;      // n-tile == id mod n_tiles keeps one table stream per XCD L2
+    const int lines = 1 << p.bits;
+    const int table_u4 = lines * 8;
+    const int steps = p.taps * p.Cc;
+    const uint4 *dt = p.dt + (size_t)nt * steps * table_u4;
+    // memory operations per table copy issued by this wave (uniform in the wave)
+    const int dma_ops = (wave * 64 < table_u4 ? 1 : 0) + (wave * 64 + LINES_THREADS < table_u4 ? 1 : 0);
+
+    // byte offset in xt of (row origin + first inner index of this lane's k-sub).  REGULAR (M is a
+    // multiple of R): a lane whose rows lie beyond the matrix reads the last R rows instead.
+    uint32_t base[REGULAR ? 1 : R];
+    uint32_t row_step = 0;          // REGULAR: distance between consecutive rows of a lane
+    {
+        int r0 = mt * (128 * R) + rs * R;
+        if (REGULAR && r0 > p.M - R) r0 = p.M - R;
+#pragma unroll
+        for (int i = 0; i < (REGULAR ? 1 : R); ++i) {
+            int r = r0 + i;
+            if (r >= p.M) r = p.M - 1;
+            const int img = r / p.HoWo, pix = r - img * p.HoWo;
+            const int oy = pix / p.Wo, ox = pix - oy * p.Wo;
+            base[i] = (uint32_t)((long long)img * p.img_stride + (long long)oy * p.oy_stride + (long long)ox * p.ox_stride + j * p.Cc);
+        }
+        if (REGULAR) row_step = p.HoWo == 1 ? (uint32_t)p.img_stride : (uint32_t)p.ox_stride;
+    }
+
+    uint32_t acc[R * 8];
+#pragma unroll
+    for (int q = 0; q < R * 8; ++q) acc[q] = 0;
+
+    // Activation loads are issued with inline assembly so that the compiler does not count them: it
+    // would otherwise wait for ALL outstanding memory operations (table copies included) before the
+    // first use.  They are issued before the step's table copy, and every step ends with a wait that
+    // leaves at most that copy outstanding, so after wait_and_barrier() they have landed; the
+    // registers are passed through that wait so no use can be scheduled ahead of it.
+    auto load_acts = [&](uint32_t *aw, int tap, int t4) {
+        const int ky = tap / p.kw, kx = tap - ky * p.kw;
+        const int8_t *xrow = p.xt + (ky * p.ky_stride + kx * p.kx_stride) + t4;
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            if (REGULAR) {
+                const int8_t *srow = xrow + (size_t)i * row_step;
+                asm volatile("global_load_dword %0, %1, %2" : "=v"(aw[i]) : "v"(base[0]), "s"(srow));
+            } else {
+                asm volatile("global_load_dword %0, %1, %2" : "=v"(aw[i]) : "v"(base[i]), "s"(xrow));
+            }
+        }
+    };
+    auto tie = [&](uint32_t *aw) {
+#pragma unroll
+        for (int i = 0; i < R; ++i) asm volatile("" : "+v"(aw[i]));
+    };
+
+    // prologue: tables of steps 0 and 1, activations of the first group
+    table_dma(dt, tbl, table_u4, wave, lane);
+    if (steps > 1) table_dma(dt + table_u4, tbl + TABLE_U4_MAX, table_u4, wave, lane);
+    uint32_t aw[R], awn[R];
+    load_acts(aw, 0, 0);
+    wait_vm(0);
+    __builtin_amdgcn_s_barrier();
+    tie(aw);
+
+    const uint32_t colbase = (uint32_t)j * 16;
+    const uint32_t ubits = (uint32_t)p.bits;
+    int tap = 0, t = 0;                     // position of the current step
+
+    // Order of this wave's memory operations: per step the table copy (dma_ops operations) first,
+    // then, in the first step of a group of four, the R activation loads of the NEXT group.
+    const bool fetch_first = ((wave >> 2) & 1) != 0;     // waves w and w + 4 share a SIMD
+    uint4 rv[R];
+    int rd = 0, wr = 2;                     // buffer read in this step / buffer the table of step + 2 goes to
+    bool prev_loaded = false;               // did the previous step issue activation loads?
+    int ops_since_acts = 0;                 // table-copy operations issued after the latest activation loads
+    for (int step = 0; step < steps; ++step) {
+        // the table of step + 2 goes to the buffer that was read in step - 1
+        const bool more = step + 2 < steps;
+        if (more) {
+            table_dma(dt + (size_t)(step + 2) * table_u4, tbl + wr * TABLE_U4_MAX, table_u4, wave, lane);
+            ops_since_acts += dma_ops;
+        }
+        // activations of the next group of four steps are requested one group ahead
+        bool loaded = false;
+        if ((t & 3) == 0) {
+            int ntap = tap, nt4 = t + 4;
+            if (nt4 >= p.Cc) { nt4 = 0; ++ntap; }
+            if (ntap < p.taps) { load_acts(awn, ntap, nt4); loaded = true; ops_since_acts = 0; }
+        }
+        // Half of the waves of each SIMD add up the entries they fetched in the PREVIOUS step before
+        // fetching this step's, the other half fetch first and add afterwards: while one half keeps
+        // the vector ALU busy the other half keeps the LDS busy, although all meet at every barrier.
+        if (!fetch_first && step > 0) {
+#pragma unroll
+            for (int i = 0; i < R; ++i) accum8<SIGNED>(acc + i * 8, rv[i]);
+        }
+        const unsigned char *cur = reinterpret_cast<const unsigned char *>(tbl + rd * TABLE_U4_MAX) + colbase;
+        const uint32_t sh = (uint32_t)(t & 3) * 8u;
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const uint32_t a = __builtin_amdgcn_ubfe(aw[i], sh, ubits);
+            rv[i] = *reinterpret_cast<const uint4 *>(cur + (a << 7));
+        }
+        if (fetch_first) {
+#pragma unroll
+            for (int i = 0; i < R; ++i) accum8<SIGNED>(acc + i * 8, rv[i]);
+        }
+        ++t;
+        if (t == p.Cc) { t = 0; ++tap; }
+        const bool group_end = (t & 3) == 0;
+        // The table of step + 1 (copied during step - 1, before that step's activation loads) must have
+        // landed: everything issued after it may stay in flight.  At the end of a group the next
+        // activations must have landed too.
+        int keep = (more ? dma_ops : 0) + ((prev_loaded || loaded) ? R : 0);
+        if (group_end && ops_since_acts < keep) keep = ops_since_acts;
+        wait_vm(keep);
+        __builtin_amdgcn_s_barrier();
+        tie(awn);
+        prev_loaded = loaded;
+        rd = rd == 2 ? 0 : rd + 1;
+        wr = wr == 2 ? 0 : wr + 1;
+        if (group_end) {
+#pragma unroll
+            for (int i = 0; i < R; ++i) aw[i] = awn[i];
+        }
+    }
+
+    if (!fetch_first && steps > 0) {
+#pragma unroll
+        for (int i = 0; i < R; ++i) accum8<SIGNED>(acc + i * 8, rv[i]);
+    }
+
+    // reduce the partial sums of the 8 k-subs (lanes j = 0..7 of a row slot)
+#pragma unroll
+    for (int q = 0; q < R * 8; ++q) {
+        uint32_t v = acc[q];
+        v += __shfl_xor(v, 1, 64);
+        v += __shfl_xor(v, 2, 64);
+        v += __shfl_xor(v, 4, 64);
+        acc[q] = v;
+    }
+    const int n = nt * 8 + j;               // lane j stores channel j of its rows
+    if (n < p.N) {
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const int r = mt * (128 * R) + rs * R + i;
+            if (r < p.M) {
+                uint32_t v = acc[i * 8];
+#pragma unroll
+                for (int c = 1; c < 8; ++c) v = (j == c) ? acc[i * 8 + c] : v;
+                const int img = r / p.HoWo, pix = r - img * p.HoWo;
+                int32_t *q = p.out + ((size_t)img * p.N + n) * p.HoWo + pix;
+                if (p.shift < 0) *q = (int32_t)v;
+                else *q = (int32_t)((uint32_t)*q + (v << p.shift));
+            }
+        }
+    }
+}
+
+
+// The two halves of the inner loop of the fast kernel, in assembly so that their order is exactly
+// the one written (the compiler would hoist the LDS reads of the next step above the additions of
+// this one and run out of registers).
+//
+// row_add: wait until at most WAITN younger LDS reads are outstanding (then v has landed), then add
+// its eight 16-bit entries to eight accumulators: v_dot2 with the constant (1, 0) / (0, 1) extends one
+// half of a register and adds it in a single instruction.
+template <bool SIGNED, int WAITN>
+__device__ __forceinline__ void row_add(uint32_t *a, const u32x4_t &v) {
+    if (SIGNED) {
+        asm volatile("s_waitcnt lgkmcnt(%12)\n\t"
+                     "v_dot2c_i32_i16 %0, 1, %8\n\tv_dot2c_i32_i16 %1, 0x10000, %8\n\t"
+                     "v_dot2c_i32_i16 %2, 1, %9\n\tv_dot2c_i32_i16 %3, 0x10000, %9\n\t"
+                     "v_dot2c_i32_i16 %4, 1, %10\n\tv_dot2c_i32_i16 %5, 0x10000, %10\n\t"
+                     "v_dot2c_i32_i16 %6, 1, %11\n\tv_dot2c_i32_i16 %7, 0x10000, %11"
+                     : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
+                     : "v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w), "n"(WAITN));
+    } else {
+        const uint32_t c_lo = 0x00000001u, c_hi = 0x00010000u;
+        asm volatile("s_waitcnt lgkmcnt(%12)\n\t"
+                     "v_dot2_u32_u16 %0, %8, %13, %0\n\tv_dot2_u32_u16 %1, %8, %14, %1\n\t"
+                     "v_dot2_u32_u16 %2, %9, %13, %2\n\tv_dot2_u32_u16 %3, %9, %14, %3\n\t"
+                     "v_dot2_u32_u16 %4, %10, %13, %4\n\tv_dot2_u32_u16 %5, %10, %14, %5\n\t"
+                     "v_dot2_u32_u16 %6, %11, %13, %6\n\tv_dot2_u32_u16 %7, %11, %14, %7"
+                     : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
+                     : "v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w), "n"(WAITN), "v"(c_lo), "v"(c_hi));
+    }
+}
+
+// row_fetch: activation = `bits`-wide field at bit SHIFT of word; read the 16 bytes of this lane's
+// column in that activation's line.  col = LDS address of the column in line 0 of table buffer 0 or 2,
+// OFF = 0 or 32768 selects the buffer after it.
+template <int SHIFT, int OFF>
+__device__ __forceinline__ void row_fetch(u32x4_t &v, uint32_t word, uint32_t bits, uint32_t col) {
+    uint32_t tmp;
+    asm volatile("v_bfe_u32 %1, %2, %3, %4\n\t"
+                 "v_lshl_add_u32 %1, %1, 7, %5\n\t"
+                 "ds_read_b128 %0, %1 offset:%6"
+                 : "=v"(v), "=&v"(tmp)
+                 : "v"(word), "n"(SHIFT), "s"(bits), "v"(col), "n"(OFF));
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fast variant of the kernel above for the common case: the inner length per tap is a multiple of
+// 32 (Cc % 4 == 0), so groups of four steps never straddle a tap.  Four steps are unrolled; with four
+// table buffers every buffer index and every wait count is a compile-time constant.
+//
+// Software pipeline.  A lane's R rows are handled in two halves that share R/2 register quadruples.
+// In step s a wave first adds the entries of rows 0..R/2-1 (fetched during step s - 1) and, as each
+// quadruple becomes free, fetches into it the entries of a row of the second half from table s; then
+// it adds those and refills the quadruples with the first-half rows of step s + 1 from table s + 1.
+// Every LDS read thus has half a step to return, reads stay in flight across the barrier, and a wave
+// arrives at the barrier as soon as its vector-ALU work is done.  Table s + 3 is copied while step s
+// runs (into the buffer of table s - 1, which nobody reads any more).
+//
+// Invariant after the barrier that ends step s: tables s + 1 and s + 2 are complete and visible to
+// all waves.  To keep it, before that barrier every wave waits for ITS part of table s + 2 (issued in
+// step s - 1).  Order of a wave's memory operations, per group g of four steps (D = copy operations
+// per table, A(g+1) = the R activation loads of the next group):
+//     u=0: D(4g+3) A(g+1)   u=1: D(4g+4)   u=2: D(4g+5)   u=3: D(4g+6)
+// Operations of one wave complete in order, so "table s + 2 has landed" means "at most as many
+// operations in flight as were issued after it": D + A at the end of u = 0 and u = 1, D at the end of
+// u = 2 (which also guarantees A(g+1), needed by the fetches of u = 3) and of u = 3.  The last two
+// groups issue fewer operations and simply wait for everything.
+// ---------------------------------------------------------------------------------------------
+template <int R, bool SIGNED, bool REGULAR, bool TWO_OPS>
+__global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const LinesParams p) {
+    __shared__ uint4 tbl[4 * TABLE_U4_MAX];          // 128 KB
+    constexpr int D = TWO_OPS ? 2 : 1;
+    // s_waitcnt immediates: vmcnt(n), expcnt and lgkmcnt left at their maxima (no wait)
+    constexpr int WAIT_DA = 0x0F70 | (D + R);
+    constexpr int WAIT_D = 0x0F70 | D;
+    constexpr int WAIT_ALL = 0x0F70;
+    static_assert(D + R < 16, "vmcnt immediate");
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int j = tid & 7;
+    const int rs = tid >> 3;
+    const int nt = blockIdx.x % p.n_tiles;
+    const int mt = blockIdx.x / p.n_tiles;
+    const int lines = 1 << p.bits;
+    const int table_u4 = lines * 8;
+    const int steps = p.taps * p.Cc;
+    const int groups = steps >> 2;
+    const unsigned char *dt = reinterpret_cast<const unsigned char *>(p.dt + (size_t)nt * steps * table_u4);
+    const uint32_t table_bytes = (uint32_t)table_u4 * 16u;
+
+    // table copy geometry: 8-bit tables take two operations of 64 lanes per wave, smaller tables one
+    // operation of table_u4 / 16 lanes per wave
+    const int lanes_act = TWO_OPS ? 64 : (table_u4 >> 4);
+    const bool dma_lane = TWO_OPS || lane < lanes_act;
+    const uint32_t dma_voff = (uint32_t)(wave * lanes_act + lane) * 16u;
+    const uint32_t lds_tbl = (uint32_t)(uintptr_t)(lds_void_ptr)tbl;
+    const uint32_t lds_wave = lds_tbl + (uint32_t)(wave * lanes_act) * 16u;
+    auto dma = [&](int step, int buf) {
+        const unsigned char *src = dt + (size_t)step * table_bytes;
+        const uint32_t m0v = lds_wave + (uint32_t)buf * (TABLE_U4_MAX * 16u);
+        if (dma_lane) {
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(dma_voff), "s"(src), "s"(m0v) : "memory", "m0");
+            if (TWO_OPS)
+                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(dma_voff), "s"(src + 16384), "s"(m0v + 16384u) : "memory", "m0");
+        }
+    };
+
+    uint32_t base[REGULAR ? 1 : R];
+    uint32_t row_step = 0;
+    {
+        int r0 = mt * (128 * R) + rs * R;
+        if (REGULAR && r0 > p.M - R) r0 = p.M - R;
+#pragma unroll
+        for (int i = 0; i < (REGULAR ? 1 : R); ++i) {
+            int r = r0 + i;
+            if (r >= p.M) r = p.M - 1;
+            const int img = r / p.HoWo, pix = r - img * p.HoWo;
+            const int oy = pix / p.Wo, ox = pix - oy * p.Wo;
+            base[i] = (uint32_t)((long long)img * p.img_stride + (long long)oy * p.oy_stride + (long long)ox * p.ox_stride + j * p.Cc);
+        }
+        if (REGULAR) row_step = p.HoWo == 1 ? (uint32_t)p.img_stride : (uint32_t)p.ox_stride;
+    }
+    auto load_acts = [&](uint32_t *aw, const int8_t *xrow) {
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            if (REGULAR) {
+                const int8_t *srow = xrow + (size_t)i * row_step;
+                asm volatile("global_load_dword %0, %1, %2" : "=v"(aw[i]) : "v"(base[0]), "s"(srow));
+            } else {
+                asm volatile("global_load_dword %0, %1, %2" : "=v"(aw[i]) : "v"(base[i]), "s"(xrow));
+            }
+        }
+    };
+    auto tie = [&](uint32_t *aw) {
+#pragma unroll
+        for (int i = 0; i < R; ++i) asm volatile("" : "+v"(aw[i]));
+    };
+
+    uint32_t acc[R * 8];
+#pragma unroll
+    for (int q = 0; q < R * 8; ++q) acc[q] = 0;
+
+    // position of the NEXT group's activations
+    int kx = 0, t4 = 0;
+    uint32_t tapoff = 0, rowoff = 0;           // kx * kx_stride + ky * ky_stride, split so both advance by additions
+    auto advance_group = [&]() {
+        t4 += 4;
+        if (t4 == p.Cc) {
+            t4 = 0;
+            ++kx;
+            tapoff += (uint32_t)p.kx_stride;
+            if (kx == p.kw) { kx = 0; rowoff += (uint32_t)p.ky_stride; tapoff = rowoff; }
+        }
+    };
+
+    // prologue: tables of steps 0..2, activations of group 0
+    dma(0, 0);
+    if (steps > 1) dma(1, 1);
+    if (steps > 2) dma(2, 2);
+    uint32_t aw[R], awn[R];
+    load_acts(aw, p.xt);
+    __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+    __builtin_amdgcn_s_barrier();
+    tie(aw);
+    advance_group();
+
+    const uint32_t ubits = (uint32_t)p.bits;
+    // LDS address of this lane's column in table buffers 0 and 2 (buffers 1 and 3 lie 32768 bytes after them)
+    const uint32_t cb0 = lds_tbl + (uint32_t)j * 16u;
+    const uint32_t cb2 = cb0 + 2u * (TABLE_U4_MAX * 16u);
+    constexpr int H = R / 2;                // rows per half
+    constexpr int WN = H - 1;               // younger LDS reads that may be in flight when a row is added
+    u32x4_t rv[H];
+    // first-half entries of step 0
+#pragma unroll
+    for (int i = 0; i < H; ++i) row_fetch<0, 0>(rv[i], aw[i], ubits, cb0);
+
+    for (int g = 0; g < groups; ++g) {
+        const int s0 = g << 2;
+        const bool last = g == groups - 1;
+        const bool tail = g >= groups - 2;      // not every operation of the steady-state schedule is issued
+        // u = 0: table buffers 0 (this step) and 1 (next step)
+        if (s0 + 3 < steps) dma(s0 + 3, 3);
+        if (!last) load_acts(awn, p.xt + tapoff + t4);
+#pragma unroll
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<0, 0>(rv[i], aw[H + i], ubits, cb0); }
+#pragma unroll
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<8, 32768>(rv[i], aw[i], ubits, cb0); }
+        if (tail) __builtin_amdgcn_s_waitcnt(WAIT_ALL); else __builtin_amdgcn_s_waitcnt(WAIT_DA);
+        __builtin_amdgcn_s_barrier();
+        // u = 1: buffers 1 and 2
+        if (s0 + 4 < steps) dma(s0 + 4, 0);
+#pragma unroll
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<8, 32768>(rv[i], aw[H + i], ubits, cb0); }
+#pragma unroll
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<16, 0>(rv[i], aw[i], ubits, cb2); }
+        if (tail) __builtin_amdgcn_s_waitcnt(WAIT_ALL); else __builtin_amdgcn_s_waitcnt(WAIT_DA);
+        __builtin_amdgcn_s_barrier();
+        // u = 2: buffers 2 and 3
+        if (s0 + 5 < steps) dma(s0 + 5, 1);
+#pragma unroll
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<16, 0>(rv[i], aw[H + i], ubits, cb2); }
+#pragma unroll
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<24, 32768>(rv[i], aw[i], ubits, cb2); }
+        if (tail) __builtin_amdgcn_s_waitcnt(WAIT_ALL); else __builtin_amdgcn_s_waitcnt(WAIT_D);
+        __builtin_amdgcn_s_barrier();
+        tie(awn);
+        // u = 3: buffers 3 and 0; the second-half fetches are the first rows of the next group's first step
+        if (s0 + 6 < steps) dma(s0 + 6, 2);
+#pragma unroll
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<24, 32768>(rv[i], aw[H + i], ubits, cb2); }
+        if (!last) {
+#pragma unroll
+            for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<0, 0>(rv[i], awn[i], ubits, cb0); }
+        } else {
+#pragma unroll
+            for (int i = 0; i < H; ++i) row_add<SIGNED, 0>(acc + (H + i) * 8, rv[i]);
+        }
+        if (tail) __builtin_amdgcn_s_waitcnt(WAIT_ALL); else __builtin_amdgcn_s_waitcnt(WAIT_D);
+        __builtin_amdgcn_s_barrier();
+#pragma unroll
+        for (int i = 0; i < R; ++i) aw[i] = awn[i];
+        advance_group();
+    }
+
+    // reduce the partial sums of the 8 k-subs (lanes j = 0..7 of a row slot) with lane permutes inside
+    // the vector ALU: swap within pairs, within quads, then mirror the 8-lane half row
+#pragma unroll
+    for (int q = 0; q < R * 8; ++q) {
+        int v = (int)acc[q];
+        v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);      // quad_perm [1,0,3,2]
+        v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);      // quad_perm [2,3,0,1]
+        v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);     // row_half_mirror
+        acc[q] = (uint32_t)v;
+    }
+    const int n = nt * 8 + j;               // lane j stores channel j of its rows
+    if (n < p.N) {
+        const int r0 = mt * (128 * R) + rs * R;
+        int img0 = 0, pix0 = 0;
+        if (REGULAR) { img0 = r0 / p.HoWo; pix0 = r0 - img0 * p.HoWo; }
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const int r = r0 + i;
+            if (r < p.M) {
+                uint32_t v = acc[i * 8];
+#pragma unroll
+                for (int c = 1; c < 8; ++c) v = (j == c) ? acc[i * 8 + c] : v;
+                int img, pix;
+                if (REGULAR && p.HoWo > 1) { img = img0; pix = pix0 + i; }      // R consecutive pixels of one output row
+                else { img = r / p.HoWo; pix = r - img * p.HoWo; }
+                int32_t *q = p.out + ((size_t)img * p.N + n) * p.HoWo + pix;
+                if (p.shift < 0) *q = (int32_t)v;
+                else *q = (int32_t)((uint32_t)*q + (v << p.shift));
+            }
+        }
+    }
+}
+
+}  // namespace adapt

@@ -360,3 +360,96 @@ def test_config5_dcgan_full_size(B, bits):
     for i, (g, o) in enumerate(zip(keep, want["accs"])):
         assert (host(g) == o).all(), f"layer {i}"
     assert_f32_close(host(got["out"]), want["out"])
+
+
+# ------------------------------------------------------------------ long-matrix ("lines") kernel via packed weights
+
+PACKED_LINEAR = [
+    # M, K, N  (the packed entry point always runs the long-matrix kernel, whatever M is)
+    (1, 8, 1), (5, 9, 3), (127, 32, 8), (129, 40, 9), (1024, 64, 16), (1500, 100, 20), (3000, 33, 7),
+    (4100, 96, 24), (9000, 17, 65),
+]
+
+
+@pytest.mark.parametrize("bits", [2, 6, 7, 8])
+@pytest.mark.parametrize("shape", PACKED_LINEAR)
+def test_linear_packed_bit_exact(B, bits, shape):
+    M, K, N = shape
+    rng = np.random.default_rng(bits * 7919 + M + 3 * K + 5 * N)
+    A = wl.random_i8(rng, (M, K), bits, "gauss" if M % 2 else "uniform")
+    W = wl.random_i8(rng, (N, K), bits)
+    n = 1 << bits
+    lut = rng.integers(-32768, 32768, size=(n, n)).astype(np.int32)
+    L = B.Lut(lut, bits)
+    pw = B.adapt_weights_pack_linear(L, dev(W))
+    got = host(B.adapt_approx_linear_packed(pw, dev(A)))
+    assert (got == orc.approx_linear(lut, bits, A, W, threads=4)).all()
+
+
+def test_linear_long_routes_through_lines_kernel_and_split_tables(B):
+    rng = np.random.default_rng(99)
+    for bits, wide in ((8, False), (8, True), (5, True)):
+        n = 1 << bits
+        lim = 2**31 - 1 if wide else 32767
+        lut = rng.integers(-lim - 1, lim, size=(n, n), dtype=np.int64).astype(np.int32)
+        L = B.Lut(lut, bits)
+        for (M, K, N) in [(4096, 64, 8), (5000, 70, 19)]:
+            A = wl.random_i8(rng, (M, K), bits)
+            W = wl.random_i8(rng, (N, K), bits)
+            want = orc.approx_linear(lut, bits, A, W, threads=4)
+            assert (host(B.adapt_approx_linear(L, dev(A), dev(W))) == want).all()
+            pw = B.adapt_weights_pack_linear(L, dev(W))
+            assert (host(B.adapt_approx_linear_packed(pw, dev(A))) == want).all()
+
+
+PACKED_CONV = [
+    # N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw
+    (1, 8, 4, 4, 8, 3, 3, 1, 1, 1, 1, 1, 1),
+    (2, 3, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, 1),
+    (1, 4, 9, 7, 6, 3, 3, 2, 2, 1, 1, 1, 1),
+    (2, 2, 6, 10, 3, 1, 1, 1, 1, 0, 0, 1, 1),
+    (1, 3, 7, 7, 2, 5, 3, 2, 1, 2, 0, 1, 1),
+    (1, 4, 8, 8, 8, 3, 3, 1, 1, 2, 2, 2, 2),
+    (3, 16, 32, 32, 16, 3, 3, 1, 1, 1, 1, 1, 1),
+    (2, 16, 32, 32, 32, 3, 3, 2, 2, 1, 1, 1, 1),
+    (5, 7, 13, 11, 19, 3, 3, 1, 1, 1, 1, 1, 1),
+    (2, 40, 20, 20, 12, 3, 3, 1, 1, 1, 1, 1, 1),
+    (8, 64, 32, 32, 64, 3, 3, 1, 1, 1, 1, 1, 1),
+]
+
+
+@pytest.mark.parametrize("bits", [6, 8])
+@pytest.mark.parametrize("case", PACKED_CONV)
+def test_conv2d_packed_bit_exact(B, bits, case):
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw_, dh, dw = case
+    rng = np.random.default_rng(bits + 17 * sum(case))
+    x = wl.random_i8(rng, (N, Cin, H, W), bits, "gauss")
+    w = wl.random_i8(rng, (Cout, Cin, kh, kw), bits, "gauss")
+    lut = wl.make_lut(bits)
+    L = B.Lut(lut, bits)
+    pk = B.adapt_weights_pack_conv2d(L, dev(w))
+    got = host(B.adapt_approx_conv2d_packed(pk, dev(x), (sh, sw), (ph, pw_), (dh, dw)))
+    want = orc.approx_conv2d(lut, bits, x, w, (sh, sw), (ph, pw_), (dh, dw), threads=8)
+    assert got.shape == want.shape and (got == want).all()
+    # plain entry point (routes by size) gives the same integers
+    assert (host(B.adapt_approx_conv2d(L, dev(x), dev(w), (sh, sw), (ph, pw_), (dh, dw))) == want).all()
+
+
+def test_packed_constant_table_counts_padding(B):
+    t = np.full((16, 16), 7, dtype=np.int32)
+    rng = np.random.default_rng(5)
+    x = wl.random_i8(rng, (2, 5, 6, 6), 4)
+    w = wl.random_i8(rng, (3, 5, 3, 3), 4)
+    pk = B.adapt_weights_pack_conv2d(B.Lut(t, 4), dev(w))
+    got = host(B.adapt_approx_conv2d_packed(pk, dev(x), (1, 1), (1, 1)))
+    assert (got == 7 * 5 * 9).all()          # padded taps are looked up; padded channels/steps are not
+
+
+def test_packed_handle_errors(B):
+    L = B.Lut(wl.make_lut(6), 6)
+    w = torch.zeros((4, 8), dtype=torch.int8, device="cuda")
+    pw = B.adapt_weights_pack_linear(L, w)
+    x = torch.zeros((1, 8, 5, 5), dtype=torch.int8, device="cuda")
+    out = torch.zeros((1, 4, 5, 5), dtype=torch.int32, device="cuda")
+    rc = B.load().adapt_approx_conv2d_packed(pw.handle, x.data_ptr(), out.data_ptr(), 1, 5, 5, 1, 1, 0, 0, 1, 1, None)
+    assert rc == -1          # linear handle used for a convolution
