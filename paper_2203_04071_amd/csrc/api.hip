@@ -289,8 +289,17 @@ int launch_lines_inst(const adapt::LinesParams &p, unsigned grid, hipStream_t s)
 
 template <int R, bool SIGNED, bool REGULAR>
 int launch_lines_fast(const adapt::LinesParams &p, unsigned grid, hipStream_t s) {
-    if (p.bits == 8) adapt::lut_lines_fast_kernel<R, SIGNED, REGULAR, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
-    else adapt::lut_lines_fast_kernel<R, SIGNED, REGULAR, false><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    if (p.bits == 8) adapt::lut_lines_fast_kernel<R, SIGNED, REGULAR, true, false><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    else adapt::lut_lines_fast_kernel<R, SIGNED, REGULAR, false, false><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+// x-major activation copy: 8 regular rows per lane
+template <bool SIGNED>
+int launch_lines_xmajor(const adapt::LinesParams &p, unsigned grid, hipStream_t s) {
+    if (p.bits == 8) adapt::lut_lines_fast_kernel<8, SIGNED, true, true, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    else adapt::lut_lines_fast_kernel<8, SIGNED, true, false, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
     HIP_TRY(hipGetLastError());
     return ADAPT_OK;
 }
@@ -338,25 +347,34 @@ struct LinesCall {       // per-call geometry of the activation side
     int M, HoWo, Wo;
     long long img_stride;
     int oy_stride, ox_stride, ky_stride, kx_stride;
+    int xmajor, ch_stride;  // x-major activation copy (see pad_channels_last_kernel) and its bytes per channel step
 };
+
+int device_cus() {
+    int cu = 256, dev = 0;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
+    return cu;
+}
+
+// rows per lane: as many as still give every compute unit a workgroup
+int lines_rows_per_lane(int M, int n_tiles) {
+    const int cu = device_cus();
+    int R = 8;
+    while (R > 2 && (long long)((M + 128 * R - 1) / (128 * R)) * n_tiles < cu) R /= 2;
+    return R;
+}
 
 int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *xt, const LinesCall &c,
               int32_t *out, hipStream_t s) {
-    int cu = 256;
-    {
-        int dev = 0;
-        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
-    }
-    // rows per lane: as many as still give every compute unit a workgroup
-    int R = 8;
+    const int R = lines_rows_per_lane(c.M, q.n_tiles);
     auto wgs = [&](int r) { return (long long)((c.M + 128 * r - 1) / (128 * r)) * q.n_tiles; };
-    while (R > 2 && wgs(R) < cu) R /= 2;
     adapt::LinesParams p;
     p.xt = xt; p.out = out;
     p.M = c.M; p.N = q.N; p.n_tiles = q.n_tiles;
     p.Cc = q.Cc; p.taps = q.kh * q.kw; p.kw = q.kw; p.bits = bits;
     p.HoWo = c.HoWo; p.Wo = c.Wo; p.img_stride = c.img_stride;
     p.oy_stride = c.oy_stride; p.ox_stride = c.ox_stride; p.ky_stride = c.ky_stride; p.kx_stride = c.kx_stride;
+    p.ch_stride = c.ch_stride;
     const long long grid = wgs(R);
     if (grid > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "lines path: grid too large");
     // one base offset per lane is enough when the R rows of a lane are equally spaced in xt
@@ -366,7 +384,8 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
         p.dt = dt[half];
         p.shift = half == 0 ? -1 : 16;
         const bool sgn = storage == 0 || half == 1;
-        if (R == 8) rc = launch_lines_r<8>(p, (unsigned)grid, sgn, regular, s);
+        if (c.xmajor) rc = sgn ? launch_lines_xmajor<true>(p, (unsigned)grid, s) : launch_lines_xmajor<false>(p, (unsigned)grid, s);
+        else if (R == 8) rc = launch_lines_r<8>(p, (unsigned)grid, sgn, regular, s);
         else if (R == 4) rc = launch_lines_r<4>(p, (unsigned)grid, sgn, regular, s);
         else rc = launch_lines_r<2>(p, (unsigned)grid, sgn, regular, s);
     }
@@ -389,6 +408,7 @@ int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     LinesCall c;
     c.M = M; c.HoWo = 1; c.Wo = 1; c.img_stride = Kp;
     c.oy_stride = c.ox_stride = c.ky_stride = c.kx_stride = 0;
+    c.xmajor = 0; c.ch_stride = 0;
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s);
     if (tmp) {
         hipError_t fe = hipFreeAsync(tmp, s);
@@ -402,18 +422,25 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
                  int W, int Ho, int Wo, int sh, int sw, int ph, int pw, int dh, int dw, hipStream_t s) {
     const int Hp = H + 2 * ph, Wp = W + 2 * pw, Cp = q.Cp;
     const size_t xt_bytes = (size_t)N * Hp * Wp * Cp;
+    // With 8 rows per lane that are 8 consecutive output pixels of a stride-1 convolution, the copy is laid
+    // out so that these rows' activations are contiguous (one wide load per lane instead of one per row).
+    const int M = N * Ho * Wo;
+    const int xmajor = (lines_rows_per_lane(M, q.n_tiles) == 8 && Wo % 8 == 0 && sw == 1 && q.Cc % 4 == 0) ? 1 : 0;
     int8_t *xt = nullptr;
-    HIP_TRY(hipMallocAsync((void **)&xt, xt_bytes + 16, s));
+    HIP_TRY(hipMallocAsync((void **)&xt, xt_bytes + 64, s));
     {
         const size_t total = xt_bytes / 4;
         size_t blocks = (total + 255) / 256;
         if (blocks > 65536) blocks = 65536;
-        adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(x, xt, N, q.Cin, H, W, ph, pw, Cp);
+        adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(x, xt, N, q.Cin, H, W, ph, pw, Cp, xmajor);
     }
     LinesCall c;
-    c.M = N * Ho * Wo; c.HoWo = Ho * Wo; c.Wo = Wo;
+    c.M = M; c.HoWo = Ho * Wo; c.Wo = Wo;
     c.img_stride = (long long)Hp * Wp * Cp;
-    c.oy_stride = sh * Wp * Cp; c.ox_stride = sw * Cp; c.ky_stride = dh * Wp * Cp; c.kx_stride = dw * Cp;
+    c.oy_stride = sh * Wp * Cp; c.ky_stride = dh * Wp * Cp;
+    c.ox_stride = xmajor ? 4 * sw : sw * Cp;
+    c.kx_stride = xmajor ? 4 * dw : dw * Cp;
+    c.xmajor = xmajor; c.ch_stride = Wp;
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s);
     hipError_t fe = hipFreeAsync(xt, s);
     if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));

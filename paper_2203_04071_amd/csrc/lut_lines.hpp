@@ -48,11 +48,15 @@ struct LinesParams {
     int oy_stride, ox_stride;   // bytes of xt per output row / column step (stride * padded width * Cp, stride * Cp)
     int ky_stride, kx_stride;   // bytes of xt per filter row / column (dilation * padded width * Cp, dilation * Cp)
     int shift;              // < 0: out = acc; >= 0: out += acc << shift
+    int ch_stride;          // x-major activation copy only: bytes per channel step (padded width); else unused
 };
 
-// NCHW int8 -> zero-padded channel-last copy [N][H + 2 ph][W + 2 pw][Cp], Cp a multiple of 8
+// NCHW int8 -> zero-padded copy, Cp (a multiple of 8) channels per pixel, in one of two orders:
+//   xmajor == 0: channel-last            [N][H + 2 ph][W + 2 pw][Cp]
+//   xmajor == 1: groups of four channels [N][H + 2 ph][Cp / 4][W + 2 pw][4]  (the four channel bytes of
+//                consecutive pixels are adjacent, so a lane's 8 rows x 4 channels are 32 contiguous bytes)
 __global__ void pad_channels_last_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ xt, int N, int C, int H,
-                                         int W, int ph, int pw, int Cp) {
+                                         int W, int ph, int pw, int Cp, int xmajor) {
     const int Hp = H + 2 * ph, Wp = W + 2 * pw;
     const size_t total = (size_t)N * Hp * Wp * (Cp / 4);
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -73,7 +77,8 @@ __global__ void pad_channels_last_kernel(const int8_t *__restrict__ x, int8_t *_
                 if (c < C) v |= (uint32_t)(uint8_t)x[(((size_t)n * C + c) * H + y) * W + xx] << (8 * q);
             }
         }
-        *reinterpret_cast<uint32_t *>(xt + (((size_t)n * Hp + yp) * Wp + xp) * Cp + c4 * 4) = v;
+        if (xmajor) *reinterpret_cast<uint32_t *>(xt + i * 4) = v;
+        else *reinterpret_cast<uint32_t *>(xt + (((size_t)n * Hp + yp) * Wp + xp) * Cp + c4 * 4) = v;
     }
 }
 
@@ -432,15 +437,17 @@ __device__ __forceinline__ void row_fetch(u32x4_t &v, uint32_t word, uint32_t bi
 // u = 2 (which also guarantees A(g+1), needed by the fetches of u = 3) and of u = 3.  The last two
 // groups issue fewer operations and simply wait for everything.
 // ---------------------------------------------------------------------------------------------
-template <int R, bool SIGNED, bool REGULAR, bool TWO_OPS>
+template <int R, bool SIGNED, bool REGULAR, bool TWO_OPS, bool XMAJOR>
 __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const LinesParams p) {
     __shared__ uint4 tbl[4 * TABLE_U4_MAX];          // 128 KB
     constexpr int D = TWO_OPS ? 2 : 1;
     // s_waitcnt immediates: vmcnt(n), expcnt and lgkmcnt left at their maxima (no wait)
-    constexpr int WAIT_DA = 0x0F70 | (D + R);
+    constexpr int A = XMAJOR ? 2 : R;                // memory operations per group of activation loads
+    constexpr int WAIT_DA = 0x0F70 | (D + A);
     constexpr int WAIT_D = 0x0F70 | D;
     constexpr int WAIT_ALL = 0x0F70;
-    static_assert(D + R < 16, "vmcnt immediate");
+    static_assert(D + A < 16, "vmcnt immediate");
+    static_assert(!XMAJOR || (REGULAR && R == 8), "x-major activations: 8 regular rows per lane");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -464,7 +471,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     const uint32_t lds_tbl = (uint32_t)(uintptr_t)(lds_void_ptr)tbl;
     const uint32_t lds_wave = lds_tbl + (uint32_t)(wave * lanes_act) * 16u;
     auto dma = [&](int step, int buf) {
-        const unsigned char *src = dt + (size_t)step * table_bytes;
+        const unsigned char *src = dt + (size_t)(unsigned)step * table_bytes;
         const uint32_t m0v = lds_wave + (uint32_t)buf * (TABLE_U4_MAX * 16u);
         if (dma_lane) {
             asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(dma_voff), "s"(src), "s"(m0v) : "memory", "m0");
@@ -484,24 +491,35 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
             if (r >= p.M) r = p.M - 1;
             const int img = r / p.HoWo, pix = r - img * p.HoWo;
             const int oy = pix / p.Wo, ox = pix - oy * p.Wo;
-            base[i] = (uint32_t)((long long)img * p.img_stride + (long long)oy * p.oy_stride + (long long)ox * p.ox_stride + j * p.Cc);
+            base[i] = (uint32_t)((long long)img * p.img_stride + (long long)oy * p.oy_stride + (long long)ox * p.ox_stride +
+                                 (XMAJOR ? j * p.Cc * p.ch_stride : j * p.Cc));
         }
         if (REGULAR) row_step = p.HoWo == 1 ? (uint32_t)p.img_stride : (uint32_t)p.ox_stride;
     }
-    auto load_acts = [&](uint32_t *aw, const int8_t *xrow) {
+    // activations of a group of four steps: element i of the register block = row i, one byte per step
+    constexpr int AQ = (R + 3) / 4;
+    auto load_acts = [&](u32x4_t *a, const int8_t *xrow) {
+        if (XMAJOR) {       // rows are consecutive pixels: 8 rows x 4 channel bytes are 32 contiguous bytes
+            asm volatile("global_load_dwordx4 %0, %2, %3\n\tglobal_load_dwordx4 %1, %2, %3 offset:16"
+                         : "=&v"(a[0]), "=&v"(a[AQ - 1])
+                         : "v"(base[0]), "s"(xrow));
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < R; ++i) {
+            uint32_t w;
             if (REGULAR) {
                 const int8_t *srow = xrow + (size_t)i * row_step;
-                asm volatile("global_load_dword %0, %1, %2" : "=v"(aw[i]) : "v"(base[0]), "s"(srow));
+                asm volatile("global_load_dword %0, %1, %2" : "=v"(w) : "v"(base[0]), "s"(srow));
             } else {
-                asm volatile("global_load_dword %0, %1, %2" : "=v"(aw[i]) : "v"(base[i]), "s"(xrow));
+                asm volatile("global_load_dword %0, %1, %2" : "=v"(w) : "v"(base[i]), "s"(xrow));
             }
+            a[i / 4][i % 4] = w;
         }
     };
-    auto tie = [&](uint32_t *aw) {
+    auto tie = [&](u32x4_t *a) {
 #pragma unroll
-        for (int i = 0; i < R; ++i) asm volatile("" : "+v"(aw[i]));
+        for (int q = 0; q < AQ; ++q) asm volatile("" : "+v"(a[q]));
     };
 
     uint32_t acc[R * 8];
@@ -509,12 +527,14 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     for (int q = 0; q < R * 8; ++q) acc[q] = 0;
 
     // position of the NEXT group's activations
-    int kx = 0, t4 = 0;
+    int kx = 0, t4 = 0, t4off = 0;             // t4off: byte offset of inner index t4 within a tap
     uint32_t tapoff = 0, rowoff = 0;           // kx * kx_stride + ky * ky_stride, split so both advance by additions
     auto advance_group = [&]() {
         t4 += 4;
+        t4off += XMAJOR ? 4 * p.ch_stride : 4;
         if (t4 == p.Cc) {
             t4 = 0;
+            t4off = 0;
             ++kx;
             tapoff += (uint32_t)p.kx_stride;
             if (kx == p.kw) { kx = 0; rowoff += (uint32_t)p.ky_stride; tapoff = rowoff; }
@@ -525,7 +545,9 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     dma(0, 0);
     if (steps > 1) dma(1, 1);
     if (steps > 2) dma(2, 2);
-    uint32_t aw[R], awn[R];
+    u32x4_t aw[AQ], awn[AQ];
+#pragma unroll
+    for (int q = 0; q < AQ; ++q) { aw[q] = u32x4_t{0, 0, 0, 0}; awn[q] = u32x4_t{0, 0, 0, 0}; }
     load_acts(aw, p.xt);
     __builtin_amdgcn_s_waitcnt(WAIT_ALL);
     __builtin_amdgcn_s_barrier();
@@ -541,7 +563,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     u32x4_t rv[H];
     // first-half entries of step 0
 #pragma unroll
-    for (int i = 0; i < H; ++i) row_fetch<0, 0>(rv[i], aw[i], ubits, cb0);
+    for (int i = 0; i < H; ++i) row_fetch<0, 0>(rv[i], aw[i / 4][i % 4], ubits, cb0);
 
     for (int g = 0; g < groups; ++g) {
         const int s0 = g << 2;
@@ -549,37 +571,37 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
         const bool tail = g >= groups - 2;      // not every operation of the steady-state schedule is issued
         // u = 0: table buffers 0 (this step) and 1 (next step)
         if (s0 + 3 < steps) dma(s0 + 3, 3);
-        if (!last) load_acts(awn, p.xt + tapoff + t4);
+        if (!last) load_acts(awn, p.xt + tapoff + t4off);
 #pragma unroll
-        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<0, 0>(rv[i], aw[H + i], ubits, cb0); }
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<0, 0>(rv[i], aw[(H + i) / 4][(H + i) % 4], ubits, cb0); }
 #pragma unroll
-        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<8, 32768>(rv[i], aw[i], ubits, cb0); }
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<8, 32768>(rv[i], aw[i / 4][i % 4], ubits, cb0); }
         if (tail) __builtin_amdgcn_s_waitcnt(WAIT_ALL); else __builtin_amdgcn_s_waitcnt(WAIT_DA);
         __builtin_amdgcn_s_barrier();
         // u = 1: buffers 1 and 2
         if (s0 + 4 < steps) dma(s0 + 4, 0);
 #pragma unroll
-        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<8, 32768>(rv[i], aw[H + i], ubits, cb0); }
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<8, 32768>(rv[i], aw[(H + i) / 4][(H + i) % 4], ubits, cb0); }
 #pragma unroll
-        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<16, 0>(rv[i], aw[i], ubits, cb2); }
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<16, 0>(rv[i], aw[i / 4][i % 4], ubits, cb2); }
         if (tail) __builtin_amdgcn_s_waitcnt(WAIT_ALL); else __builtin_amdgcn_s_waitcnt(WAIT_DA);
         __builtin_amdgcn_s_barrier();
         // u = 2: buffers 2 and 3
         if (s0 + 5 < steps) dma(s0 + 5, 1);
 #pragma unroll
-        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<16, 0>(rv[i], aw[H + i], ubits, cb2); }
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<16, 0>(rv[i], aw[(H + i) / 4][(H + i) % 4], ubits, cb2); }
 #pragma unroll
-        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<24, 32768>(rv[i], aw[i], ubits, cb2); }
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<24, 32768>(rv[i], aw[i / 4][i % 4], ubits, cb2); }
         if (tail) __builtin_amdgcn_s_waitcnt(WAIT_ALL); else __builtin_amdgcn_s_waitcnt(WAIT_D);
         __builtin_amdgcn_s_barrier();
         tie(awn);
         // u = 3: buffers 3 and 0; the second-half fetches are the first rows of the next group's first step
         if (s0 + 6 < steps) dma(s0 + 6, 2);
 #pragma unroll
-        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<24, 32768>(rv[i], aw[H + i], ubits, cb2); }
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<24, 32768>(rv[i], aw[(H + i) / 4][(H + i) % 4], ubits, cb2); }
         if (!last) {
 #pragma unroll
-            for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<0, 0>(rv[i], awn[i], ubits, cb0); }
+            for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<0, 0>(rv[i], awn[i / 4][i % 4], ubits, cb0); }
         } else {
 #pragma unroll
             for (int i = 0; i < H; ++i) row_add<SIGNED, 0>(acc + (H + i) * 8, rv[i]);
@@ -587,7 +609,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
         if (tail) __builtin_amdgcn_s_waitcnt(WAIT_ALL); else __builtin_amdgcn_s_waitcnt(WAIT_D);
         __builtin_amdgcn_s_barrier();
 #pragma unroll
-        for (int i = 0; i < R; ++i) aw[i] = awn[i];
+        for (int q = 0; q < AQ; ++q) aw[q] = awn[q];
         advance_group();
     }
 
@@ -606,19 +628,43 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
         const int r0 = mt * (128 * R) + rs * R;
         int img0 = 0, pix0 = 0;
         if (REGULAR) { img0 = r0 / p.HoWo; pix0 = r0 - img0 * p.HoWo; }
+        if constexpr (XMAJOR) {
+            // 8 consecutive pixels of one output row and one channel
+            uint32_t v[8];
 #pragma unroll
-        for (int i = 0; i < R; ++i) {
-            const int r = r0 + i;
-            if (r < p.M) {
-                uint32_t v = acc[i * 8];
+            for (int i = 0; i < 8; ++i) {
+                v[i] = acc[i * 8];
 #pragma unroll
-                for (int c = 1; c < 8; ++c) v = (j == c) ? acc[i * 8 + c] : v;
-                int img, pix;
-                if (REGULAR && p.HoWo > 1) { img = img0; pix = pix0 + i; }      // R consecutive pixels of one output row
-                else { img = r / p.HoWo; pix = r - img * p.HoWo; }
-                int32_t *q = p.out + ((size_t)img * p.N + n) * p.HoWo + pix;
-                if (p.shift < 0) *q = (int32_t)v;
-                else *q = (int32_t)((uint32_t)*q + (v << p.shift));
+                for (int c = 1; c < 8; ++c) v[i] = (j == c) ? acc[i * 8 + c] : v[i];
+            }
+            int32_t *q0 = p.out + ((size_t)img0 * p.N + n) * p.HoWo + pix0;
+            if (r0 + 8 <= p.M) {
+                if (p.shift < 0 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {       // two 16-byte stores
+                    reinterpret_cast<uint4 *>(q0)[0] = make_uint4(v[0], v[1], v[2], v[3]);
+                    reinterpret_cast<uint4 *>(q0)[1] = make_uint4(v[4], v[5], v[6], v[7]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        if (p.shift < 0) q0[i] = (int32_t)v[i];
+                        else q0[i] = (int32_t)((uint32_t)q0[i] + (v[i] << p.shift));
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < R; ++i) {
+                const int r = r0 + i;
+                if (r < p.M) {
+                    uint32_t v = acc[i * 8];
+#pragma unroll
+                    for (int c = 1; c < 8; ++c) v = (j == c) ? acc[i * 8 + c] : v;
+                    int img, pix;
+                    if (REGULAR && p.HoWo > 1) { img = img0; pix = pix0 + i; }      // R consecutive pixels of one output row
+                    else { img = r / p.HoWo; pix = r - img * p.HoWo; }
+                    int32_t *q = p.out + ((size_t)img * p.N + n) * p.HoWo + pix;
+                    if (p.shift < 0) *q = (int32_t)v;
+                    else *q = (int32_t)((uint32_t)*q + (v << p.shift));
+                }
             }
         }
     }
