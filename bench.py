@@ -7,6 +7,7 @@ configurations).  Default workload: the 3x3 convolution layer the metric is quot
 (batch 32, 64 -> 64 channels, 32x32, 8-bit table).  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1|2|3|4|5] [--bits B] [--no-cpu-baseline]
+                  [--copy-calibration]
 """
 from __future__ import annotations
 
@@ -24,6 +25,11 @@ sys.path.insert(0, ROOT)
 LDS_LANES_PER_CLK_PER_CU = 32      # 32 banks x 4 B: one 16-bit gather lane per bank per clock
 MODEL_CLOCK_GHZ = 2.4
 MODEL_CUS = 256
+
+# HBM bytes per launch of the dominant call, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, each
+# scaled by what the same counter reads for a plain 64 MiB copy (--copy-calibration); figures and commands are in
+# profiles/lut_lines_fast_config2.md.  Keyed by config number; None = not measured.
+MEASURED_TRAFFIC_BYTES = {2: (20279 * 2.0 + 13312 * 1.0 + 4637 * 2.0 + 2312 * 1.0) * 1024}
 
 
 def _f(x):
@@ -158,6 +164,8 @@ def main():
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--bits", type=int, default=8, help="table bits for config 5 (6 or 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run three plain 64 MiB device-to-device copies (what FETCH_SIZE / WRITE_SIZE are scaled by)")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc (reported as roofline.traffic)")
     args = ap.parse_args()
@@ -171,6 +179,14 @@ def main():
         raise SystemExit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     B.load()
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        a = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": 64 << 20, "copies": 3}))
+        return
     step, core, macs, name, _keep = build_step(args.config, args.bits, torch, B, gnet, wl)
 
     for _ in range(args.warmup):
@@ -186,26 +202,31 @@ def main():
     # dominant kernel: HIP events on the launch stream around the table-lookup call
     roof = None
     cus = B.adapt_device_cu_count()
+    traffic = args.traffic_bytes if args.traffic_bytes is not None else MEASURED_TRAFFIC_BYTES.get(args.config)
     peak = cus * LDS_LANES_PER_CLK_PER_CU * MODEL_CLOCK_GHZ * 1e9
     if core is not None:
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        # back-to-back launches between one pair of events per block, so the queue stays full and the figure is the
+        # device time of the call's kernels, comparable with a kernel trace
+        blocks, per = 5, max(1, args.steps // 5)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(blocks)]
         torch.cuda.synchronize()
         for a, b in evs:
             a.record()
-            core()
+            for _ in range(per):
+                core()
             b.record()
         torch.cuda.synchronize()
-        kms = np.array([a.elapsed_time(b) for a, b in evs])
+        kms = np.array([a.elapsed_time(b) / per for a, b in evs])
         k_avg = float(kms.mean())
         achieved = macs / (k_avg * 1e-3)
         roof = dict(bound="lds", achieved=achieved / 1e12, peak=peak / 1e12, unit="Tlookup/s", frac=achieved / peak,
-                    traffic=args.traffic_bytes, kernel_ms_avg=k_avg, kernel_ms_min=float(kms.min()),
+                    traffic=traffic, kernel_ms_avg=k_avg, kernel_ms_min=float(kms.min()),
                     peak_model=f"{cus} CUs x {LDS_LANES_PER_CLK_PER_CU} LDS bank-lanes/clk x {MODEL_CLOCK_GHZ} GHz; "
                                "1 lookup (2 B) per LUT-MAC")
     else:
         achieved = macs / (ms_per_step * 1e-3)
         roof = dict(bound="lds", achieved=achieved / 1e12, peak=peak / 1e12, unit="Tlookup/s", frac=achieved / peak,
-                    traffic=args.traffic_bytes, note="whole network step (all kernels) against the LDS lookup peak")
+                    traffic=traffic, note="whole network step (all kernels) against the LDS lookup peak")
 
     out = {
         "metric": "approximate MACs/sec (LUT-MAC/s), whole step: quantise + table-lookup layer(s) + dequantise",
