@@ -132,12 +132,23 @@ int adapt_weights_pack_linear(adapt_weights **out, const adapt_lut *lut, const i
 /* w_dev [Cout][Cin][kh][kw] (groups = 1) */
 int adapt_weights_pack_conv2d(adapt_weights **out, const adapt_lut *lut, const int8_t *w_dev, int Cout, int Cin,
                               int kh, int kw, void *stream);
+/* w_dev [Cin][Cout][kh][kw], transposed convolution with the given stride (Sec. V generator networks).  When kh and kw
+ * are multiples of the stride the layer is stored as stride^2 ordinary stride-1 convolutions (one per residue of the
+ * output position modulo the stride), each over kh/stride x kw/stride taps.  The handle also keeps a copy of the
+ * weights and a pointer to `lut` for geometries that form does not cover (a single input pixel, kernel or output sizes
+ * that are no multiple of the stride): the table handle must stay alive as long as this handle is used. */
+int adapt_weights_pack_conv_transpose2d(adapt_weights **out, const adapt_lut *lut, const int8_t *w_dev, int Cin, int Cout,
+                                        int kh, int kw, int stride, void *stream);
 int adapt_weights_destroy(adapt_weights *w);
 
 /* same results as adapt_approx_linear / adapt_approx_conv2d with the weights and table given at pack time */
 int adapt_approx_linear_packed(const adapt_weights *w, const int8_t *a_dev, int32_t *acc_dev, int M, void *stream);
 int adapt_approx_conv2d_packed(const adapt_weights *w, const int8_t *x_dev, int32_t *acc_dev, int N, int H, int W,
                                int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, void *stream);
+
+/* same results as adapt_approx_conv_transpose2d (real pairs only: no term for a tap without an input pixel) */
+int adapt_approx_conv_transpose2d_packed(const adapt_weights *w, const int8_t *x_dev, int32_t *acc_dev, int N, int H, int W,
+                                         int pad, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
  * fp32 operations between approximate layers.  Each element is produced by single IEEE fp32

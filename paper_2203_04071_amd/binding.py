@@ -24,8 +24,9 @@ EXPORTS = [
     "adapt_lut_create", "adapt_lut_destroy", "adapt_lut_info",
     "adapt_absmax_f32", "adapt_quantize_f32", "adapt_dequant_i32",
     "adapt_approx_linear", "adapt_approx_conv2d", "adapt_approx_conv_transpose2d",
-    "adapt_weights_pack_linear", "adapt_weights_pack_conv2d", "adapt_weights_destroy",
-    "adapt_approx_linear_packed", "adapt_approx_conv2d_packed",
+    "adapt_weights_pack_linear", "adapt_weights_pack_conv2d", "adapt_weights_pack_conv_transpose2d",
+    "adapt_weights_destroy",
+    "adapt_approx_linear_packed", "adapt_approx_conv2d_packed", "adapt_approx_conv_transpose2d_packed",
     "adapt_relu_f32", "adapt_add_f32", "adapt_avgpool_hw_f32", "adapt_shortcut_a_f32",
     "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32",
 ]
@@ -65,6 +66,8 @@ def load() -> ctypes.CDLL:
     L.adapt_approx_conv_transpose2d.argtypes = [vp, vp, vp, vp] + [i32] * 9 + [vp]
     L.adapt_weights_pack_linear.argtypes = [ctypes.POINTER(vp), vp, vp, i32, i32, vp]
     L.adapt_weights_pack_conv2d.argtypes = [ctypes.POINTER(vp), vp, vp, i32, i32, i32, i32, vp]
+    L.adapt_weights_pack_conv_transpose2d.argtypes = [ctypes.POINTER(vp), vp, vp, i32, i32, i32, i32, i32, vp]
+    L.adapt_approx_conv_transpose2d_packed.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
     L.adapt_weights_destroy.argtypes = [vp]
     L.adapt_approx_linear_packed.argtypes = [vp, vp, vp, i32, vp]
     L.adapt_approx_conv2d_packed.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
@@ -143,10 +146,12 @@ def conv_out_hw(H, W, kh, kw, sh, sw, ph, pw, dh=1, dw=1):
 class PackedWeights:
     """Owner of an adapt_weights handle (weights of one layer combined with one table)."""
 
-    def __init__(self, lut: Lut, w, kind: str, stream=None):
+    def __init__(self, lut: Lut, w, kind: str, stream=None, stride: int = 1):
         self._h = ctypes.c_void_p()
         self.kind = kind
         self.shape = tuple(w.shape)
+        self.stride = stride
+        self._lut = lut         # the library keeps a pointer to the table handle of a transposed-convolution layer
         if kind == "linear":
             N, K = w.shape
             _chk(load().adapt_weights_pack_linear(ctypes.byref(self._h), lut.handle, _ptr(w, torch.int8), K, N,
@@ -155,6 +160,10 @@ class PackedWeights:
             Cout, Cin, kh, kw = w.shape
             _chk(load().adapt_weights_pack_conv2d(ctypes.byref(self._h), lut.handle, _ptr(w, torch.int8), Cout, Cin,
                                                   kh, kw, _stream(stream)))
+        elif kind == "conv_transpose2d":
+            Cin, Cout, kh, kw = w.shape
+            _chk(load().adapt_weights_pack_conv_transpose2d(ctypes.byref(self._h), lut.handle, _ptr(w, torch.int8), Cin,
+                                                            Cout, kh, kw, stride, _stream(stream)))
         else:
             raise ValueError(kind)
 
@@ -182,6 +191,10 @@ def adapt_weights_pack_conv2d(lut: Lut, w, stream=None) -> PackedWeights:
     return PackedWeights(lut, w, "conv2d", stream)
 
 
+def adapt_weights_pack_conv_transpose2d(lut: Lut, w, stride=1, stream=None) -> PackedWeights:
+    return PackedWeights(lut, w, "conv_transpose2d", stream, stride)
+
+
 def adapt_weights_destroy(pw: PackedWeights):
     pw.close()
 
@@ -205,6 +218,18 @@ def adapt_approx_conv2d_packed(pw: PackedWeights, x, stride=(1, 1), pad=(0, 0), 
         out = torch.empty((N, Cout, Ho, Wo), dtype=torch.int32, device=x.device)
     _chk(load().adapt_approx_conv2d_packed(pw.handle, _ptr(x, torch.int8), _ptr(out, torch.int32), N, H, W, stride[0],
                                            stride[1], pad[0], pad[1], dil[0], dil[1], _stream(stream)))
+    return out
+
+
+def adapt_approx_conv_transpose2d_packed(pw: PackedWeights, x, pad=0, out=None, stream=None):
+    N, Cin, H, W = x.shape
+    Cin2, Cout, kh, kw = pw.shape
+    assert Cin == Cin2 and pw.kind == "conv_transpose2d"
+    if out is None:
+        Ho, Wo = (H - 1) * pw.stride - 2 * pad + kh, (W - 1) * pw.stride - 2 * pad + kw
+        out = torch.empty((N, Cout, Ho, Wo), dtype=torch.int32, device=x.device)
+    _chk(load().adapt_approx_conv_transpose2d_packed(pw.handle, _ptr(x, torch.int8), _ptr(out, torch.int32), N, H, W, pad,
+                                                     _stream(stream)))
     return out
 
 

@@ -56,12 +56,18 @@ struct adapt_lut {
 };
 
 struct adapt_weights {
-    int kind;               // 0 linear, 1 conv2d
+    int kind;               // 0 linear, 1 conv2d, 2 transposed conv2d
     int bits, storage, device;
     int N, Cin, kh, kw;     // linear: Cin = K, kh = kw = 1
     int Cp, Cc, n_tiles;    // padded inner length (multiple of 8; linear: of 32), steps per tap, 8-channel tiles
-    size_t dt_bytes;        // per table-half
+    size_t dt_bytes;        // per table-half (transposed convolution: all phases together)
     uint4 *dt_dev[2];
+    // transposed convolution only
+    int stride;
+    bool phased;            // kh and kw are multiples of the stride: derived tables per phase exist
+    int32_t *zsum_dev;      // [Cout][kh * kw] sums of T[0][w] over the input channels
+    int8_t *w8_dev;         // copy of the weights for the geometries the phase form does not cover
+    const adapt_lut *lut;   // the table handle (must outlive this handle), for those geometries
 };
 
 extern "C" {
@@ -217,6 +223,7 @@ struct Geometry {
     int H, W, Wo, HoWo;
     int sh, sw, ph, pw, dh, dw;
     int kstride, img_stride;
+    int wt;                 // GEMM mode only: the weights are stored [K][N] instead of [N][K]
 };
 
 // Run the rows kernel once per table image of the handle.
@@ -247,7 +254,8 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     HIP_TRY(hipMallocAsync((void **)&wofs, (size_t)Ktot * Npad * sizeof(uint32_t), s));
     const size_t pack_n = (size_t)Ktot * Npad;
     adapt::pack_row_offsets_kernel<<<(unsigned)((pack_n + 255) / 256), 256, 0, s>>>(
-        w, wofs, (int)Ktot, g.N, Npad, g.Cin, g.taps, g.mode, 1 << (bits - 1), (1 << bits) - 1, lut->rs * 2);
+        w, wofs, (int)Ktot, g.N, Npad, g.Cin, g.taps, g.wt ? (int)adapt::MODE_CONVT : g.mode, 1 << (bits - 1), (1 << bits) - 1,
+        lut->rs * 2);
     hipError_t pe = hipGetLastError();
     int rc = ADAPT_OK;
     if (pe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "pack_row_offsets launch: %s", hipGetErrorString(pe));
@@ -343,11 +351,19 @@ int pack_lines(const adapt_lut *lut, const int8_t *w, const LinesShape &q, uint4
     return ADAPT_OK;
 }
 
+struct LinesPhase {      // one stride-1 sub-convolution of a transposed convolution (plain layers: a single zero phase)
+    int xt_off = 0;         // bytes into the activation copy
+    int out_off = 0;        // elements into an output plane
+    long long dt_off = 0;   // 16-byte units into the derived tables
+};
+
 struct LinesCall {       // per-call geometry of the activation side
     int M, HoWo, Wo;
     long long img_stride;
     int oy_stride, ox_stride, ky_stride, kx_stride;
     int xmajor, ch_stride;  // x-major activation copy (see pad_channels_last_kernel) and its bytes per channel step
+    int out_plane, out_sy, out_sx;      // see adapt::LinesParams
+    std::vector<LinesPhase> phases;
 };
 
 int device_cus() {
@@ -366,8 +382,8 @@ int lines_rows_per_lane(int M, int n_tiles) {
 
 int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *xt, const LinesCall &c,
               int32_t *out, hipStream_t s) {
-    const int R = lines_rows_per_lane(c.M, q.n_tiles);
-    auto wgs = [&](int r) { return (long long)((c.M + 128 * r - 1) / (128 * r)) * q.n_tiles; };
+    const int n_phases = (int)c.phases.size();
+    const int R = lines_rows_per_lane(c.M, q.n_tiles * n_phases);
     adapt::LinesParams p;
     p.xt = xt; p.out = out;
     p.M = c.M; p.N = q.N; p.n_tiles = q.n_tiles;
@@ -375,19 +391,30 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     p.HoWo = c.HoWo; p.Wo = c.Wo; p.img_stride = c.img_stride;
     p.oy_stride = c.oy_stride; p.ox_stride = c.ox_stride; p.ky_stride = c.ky_stride; p.kx_stride = c.kx_stride;
     p.ch_stride = c.ch_stride;
-    const long long grid = wgs(R);
-    if (grid > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "lines path: grid too large");
+    p.out_plane = c.out_plane; p.out_sy = c.out_sy; p.out_sx = c.out_sx;
+    p.m_tiles = (c.M + 128 * R - 1) / (128 * R);
     // one base offset per lane is enough when the R rows of a lane are equally spaced in xt
     const bool regular = (c.M % R == 0) && (c.HoWo == 1 || c.Wo % R == 0);
+    const bool xmajor = c.xmajor && R == 8 && regular;
+    if (c.xmajor && !xmajor) return fail(ADAPT_ERR_HIP, "lines path: x-major copy without 8 regular rows per lane");
     int rc = ADAPT_OK;
-    for (int half = 0; half <= storage && rc == ADAPT_OK; ++half) {
-        p.dt = dt[half];
-        p.shift = half == 0 ? -1 : 16;
-        const bool sgn = storage == 0 || half == 1;
-        if (c.xmajor) rc = sgn ? launch_lines_xmajor<true>(p, (unsigned)grid, s) : launch_lines_xmajor<false>(p, (unsigned)grid, s);
-        else if (R == 8) rc = launch_lines_r<8>(p, (unsigned)grid, sgn, regular, s);
-        else if (R == 4) rc = launch_lines_r<4>(p, (unsigned)grid, sgn, regular, s);
-        else rc = launch_lines_r<2>(p, (unsigned)grid, sgn, regular, s);
+    for (int first = 0; first < n_phases && rc == ADAPT_OK; first += 4) {       // up to four phases per launch
+        p.phases = n_phases - first < 4 ? n_phases - first : 4;
+        for (int i = 0; i < 4; ++i) {
+            const LinesPhase &f = c.phases[first + (i < p.phases ? i : 0)];
+            p.xt_off[i] = f.xt_off; p.out_off[i] = f.out_off; p.dt_off[i] = f.dt_off;
+        }
+        const long long grid = (long long)p.m_tiles * q.n_tiles * p.phases;
+        if (grid > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "lines path: grid too large");
+        for (int half = 0; half <= storage && rc == ADAPT_OK; ++half) {
+            p.dt = dt[half];
+            p.shift = half == 0 ? -1 : 16;
+            const bool sgn = storage == 0 || half == 1;
+            if (xmajor) rc = sgn ? launch_lines_xmajor<true>(p, (unsigned)grid, s) : launch_lines_xmajor<false>(p, (unsigned)grid, s);
+            else if (R == 8) rc = launch_lines_r<8>(p, (unsigned)grid, sgn, regular, s);
+            else if (R == 4) rc = launch_lines_r<4>(p, (unsigned)grid, sgn, regular, s);
+            else rc = launch_lines_r<2>(p, (unsigned)grid, sgn, regular, s);
+        }
     }
     return rc;
 }
@@ -409,6 +436,8 @@ int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     c.M = M; c.HoWo = 1; c.Wo = 1; c.img_stride = Kp;
     c.oy_stride = c.ox_stride = c.ky_stride = c.kx_stride = 0;
     c.xmajor = 0; c.ch_stride = 0;
+    c.out_plane = 1; c.out_sy = 0; c.out_sx = 0;
+    c.phases.resize(1);
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s);
     if (tmp) {
         hipError_t fe = hipFreeAsync(tmp, s);
@@ -441,10 +470,96 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     c.ox_stride = xmajor ? 4 * sw : sw * Cp;
     c.kx_stride = xmajor ? 4 * dw : dw * Cp;
     c.xmajor = xmajor; c.ch_stride = Wp;
+    c.out_plane = Ho * Wo; c.out_sy = Wo; c.out_sx = 1;
+    c.phases.resize(1);
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s);
     hipError_t fe = hipFreeAsync(xt, s);
     if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
     return rc;
+}
+
+// Transposed convolution as stride * stride stride-1 convolutions (see pack_line_tables_convt_kernel).  Needs kernel
+// sizes that are multiples of the stride, an output size that is one too, and more than one input pixel.
+bool convt_phases_ok(int H, int W, int kh, int kw, int st, int pad) {
+    return kh % st == 0 && kw % st == 0 && (2 * pad) % st == 0 && (long long)H * W > 1;
+}
+
+LinesShape convt_phase_shape(int bits, int Cout, int Cin, int kh, int kw, int st) {
+    return lines_shape(1, bits, Cout, Cin, kh / st, kw / st);       // one phase; dt_bytes is per phase
+}
+
+int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int32_t *zsum, const int8_t *x,
+                           int32_t *out, int N, int H, int W, int kh, int kw, int st, int pad, hipStream_t s) {
+    const int Ty = q.kh, Tx = q.kw, Cp = q.Cp;
+    const int Hp = H + 2 * (Ty - 1), Wp = W + 2 * (Tx - 1);
+    const int Ho = (H - 1) * st - 2 * pad + kh, Wo = (W - 1) * st - 2 * pad + kw;
+    const int Qy = Ho / st, Qx = Wo / st;
+    const int M = N * Qy * Qx;
+    const size_t xt_bytes = (size_t)N * Hp * Wp * Cp;
+    const int xmajor = (lines_rows_per_lane(M, q.n_tiles * st * st) == 8 && Qx % 8 == 0 && q.Cc % 4 == 0) ? 1 : 0;
+    int8_t *xt = nullptr;
+    HIP_TRY(hipMallocAsync((void **)&xt, xt_bytes + 64, s));
+    {
+        const size_t total = xt_bytes / 4;
+        size_t blocks = (total + 255) / 256;
+        if (blocks > 65536) blocks = 65536;
+        adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(x, xt, N, q.Cin, H, W, Ty - 1, Tx - 1, Cp, xmajor);
+    }
+    LinesCall c;
+    c.M = M; c.HoWo = Qy * Qx; c.Wo = Qx;
+    c.img_stride = (long long)Hp * Wp * Cp;
+    c.oy_stride = c.ky_stride = Wp * Cp;
+    c.ox_stride = c.kx_stride = xmajor ? 4 : Cp;
+    c.xmajor = xmajor; c.ch_stride = Wp;
+    c.out_plane = Ho * Wo; c.out_sy = st * Wo; c.out_sx = st;
+    const long long phase_u4 = (long long)(q.dt_bytes / 16);
+    for (int ry = 0; ry < st; ++ry)
+        for (int rx = 0; rx < st; ++rx) {
+            // first window position of the phase: the smallest q with an output row s q + r - pad >= 0; in the
+            // copy (padded by T - 1) the window of that output starts at row q
+            const int qy0 = pad > ry ? (pad - ry + st - 1) / st : 0, qx0 = pad > rx ? (pad - rx + st - 1) / st : 0;
+            LinesPhase f;
+            f.xt_off = qy0 * Wp * Cp + qx0 * (xmajor ? 4 : Cp);
+            f.out_off = (st * qy0 + ry - pad) * Wo + (st * qx0 + rx - pad);
+            f.dt_off = (long long)(ry * st + rx) * phase_u4;
+            c.phases.push_back(f);
+        }
+    int rc = run_lines(bits, storage, q, dt, xt, c, out, s);
+    hipError_t fe = hipFreeAsync(xt, s);
+    if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
+    if (rc != ADAPT_OK) return rc;
+    // window taps over the zero border were looked up; the layer is defined over real pairs only
+    const int Ly = kh - st - pad > 0 ? kh - st - pad : 0, Lx = kw - st - pad > 0 ? kw - st - pad : 0;
+    const int nrows = 2 * Ly < Ho ? 2 * Ly : Ho, ncols = 2 * Lx < Wo ? 2 * Lx : Wo;
+    const size_t planes = (size_t)N * q.N;
+    const size_t work[2] = {planes * nrows * Wo, planes * (size_t)(Ho - nrows) * ncols};
+    for (int region = 0; region < 2; ++region) {
+        if (!work[region]) continue;
+        size_t blocks = (work[region] + 255) / 256;
+        if (blocks > 65536) blocks = 65536;
+        adapt::convt_border_fix_kernel<<<(unsigned)blocks, 256, 0, s>>>(out, zsum, (int)planes, q.N, Ho, Wo, H, W, kh, kw, st, pad, Ly,
+                                                                       Lx, region);
+        HIP_TRY(hipGetLastError());
+    }
+    return ADAPT_OK;
+}
+
+// derived tables of all phases + zero sums into caller-provided buffers
+int pack_convt(const adapt_lut *lut, const int8_t *w, const LinesShape &q, int kh, int kw, int st, uint4 *const dt[2], int32_t *zsum,
+               hipStream_t s) {
+    for (int half = 0; half <= lut->storage; ++half) {
+        const size_t total = q.dt_bytes / 16 * st * st;
+        size_t blocks = (total + 255) / 256;
+        if (blocks > 65536) blocks = 65536;
+        adapt::pack_line_tables_convt_kernel<<<(unsigned)blocks, 256, 0, s>>>(lut->lut16_dev[half], w, dt[half], lut->bits, q.N, q.Cin, kh,
+                                                                             kw, st, q.Cc, q.n_tiles);
+        HIP_TRY(hipGetLastError());
+    }
+    const int nz = q.N * kh * kw;
+    adapt::convt_zero_sums_kernel<<<(unsigned)((nz + 255) / 256), 256, 0, s>>>(lut->lut16_dev[0], lut->storage ? lut->lut16_dev[1] : nullptr,
+                                                                              w, zsum, lut->bits, q.N, q.Cin, kh * kw);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
 }
 
 // limits of the lines path: 32-bit byte offsets into the activation copy, and a sane table stream
@@ -481,6 +596,54 @@ int check_lut(const adapt_lut *lut, const char *who) {
     if (hipGetDevice(&dev) != hipSuccess || dev != lut->device)
         return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: table handle belongs to device %d, current device is %d", who, lut->device, dev);
     return ADAPT_OK;
+}
+
+// transposed convolution on the rows kernel
+int convt_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *acc, int N, int Cin, int H, int W, int Cout, int kh,
+               int kw, int stride, int pad, hipStream_t s) {
+    const int Ho = (H - 1) * stride - 2 * pad + kh, Wo = (W - 1) * stride - 2 * pad + kw;
+    Geometry g{};
+    if (H == 1 && W == 1 && pad == 0) {
+        // one input pixel: output pixel (ky, kx) of channel co is the inner product of the input vector with
+        // w[:, co, ky, kx] -- a linear layer with N = Cout kh kw whose weights are stored [K][N]
+        g.mode = adapt::MODE_GEMM; g.M = N; g.N = Cout * kh * kw; g.Cin = Cin; g.taps = 1; g.kw = 1;
+        g.H = 1; g.W = 1; g.Wo = 1; g.HoWo = 1; g.sh = g.sw = g.dh = g.dw = 1; g.ph = g.pw = 0;
+        g.kstride = 1; g.img_stride = Cin; g.wt = 1;
+        return run_rows(lut, x, w, acc, g, s);
+    }
+    g.mode = adapt::MODE_CONVT; g.M = N * Ho * Wo; g.N = Cout; g.Cin = Cin; g.taps = kh * kw; g.kw = kw;
+    g.H = H; g.W = W; g.Wo = Wo; g.HoWo = Ho * Wo;
+    g.sh = stride; g.sw = stride; g.ph = pad; g.pw = pad; g.dh = g.dw = 1;
+    g.kstride = H * W; g.img_stride = Cin * H * W;
+    return run_rows(lut, x, w, acc, g, s);
+}
+
+// transposed convolution with plain weights: the cheapest form the geometry allows
+int convt_any(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *acc, int N, int Cin, int H, int W, int Cout, int kh,
+              int kw, int stride, int pad, hipStream_t s) {
+    const int Ho = (H - 1) * stride - 2 * pad + kh, Wo = (W - 1) * stride - 2 * pad + kw;
+    const long long M = (long long)N * Ho * Wo;
+    if (convt_phases_ok(H, W, kh, kw, stride, pad) && M >= LINES_MIN_ROWS && Cin >= 4) {
+        const LinesShape q = convt_phase_shape(lut->bits, Cout, Cin, kh, kw, stride);
+        const long long xt_bytes = (long long)N * (H + 2LL * (q.kh - 1)) * (W + 2LL * (q.kw - 1)) * q.Cp;
+        const size_t all = q.dt_bytes * stride * stride;
+        if (lines_fits(xt_bytes, all, lut->storage)) {
+            uint4 *dt[2] = {nullptr, nullptr};
+            int32_t *zsum = nullptr;
+            int rc = ADAPT_OK;
+            hipError_t e = hipMallocAsync((void **)&zsum, (size_t)Cout * kh * kw * sizeof(int32_t), s);
+            for (int half = 0; half <= lut->storage && e == hipSuccess; ++half) e = hipMallocAsync((void **)&dt[half], all, s);
+            if (e != hipSuccess)
+                rc = fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "hipMallocAsync(tables): %s", hipGetErrorString(e));
+            if (rc == ADAPT_OK) rc = pack_convt(lut, w, q, kh, kw, stride, dt, zsum, s);
+            if (rc == ADAPT_OK) rc = lines_conv_transpose2d(lut->bits, lut->storage, q, dt, zsum, x, acc, N, H, W, kh, kw, stride, pad, s);
+            for (int half = 0; half < 2; ++half)
+                if (dt[half]) (void)hipFreeAsync(dt[half], s);
+            if (zsum) (void)hipFreeAsync(zsum, s);
+            return rc;
+        }
+    }
+    return convt_rows(lut, x, w, acc, N, Cin, H, W, Cout, kh, kw, stride, pad, s);
 }
 
 }  // namespace
@@ -560,12 +723,7 @@ int adapt_approx_conv_transpose2d(const adapt_lut *lut, const int8_t *x_dev, con
     if ((long long)N * Cout * Ho * Wo > 0x7fffffffLL || (long long)N * Cin * H * W > 0x7fffffffLL ||
         (long long)Cout * Cin * kh * kw > 0x7fffffffLL)
         return fail(ADAPT_ERR_UNSUPPORTED, "adapt_approx_conv_transpose2d: tensor with more than 2^31-1 elements");
-    Geometry g{};
-    g.mode = adapt::MODE_CONVT; g.M = (int)(N * Ho * Wo); g.N = Cout; g.Cin = Cin; g.taps = kh * kw; g.kw = kw;
-    g.H = H; g.W = W; g.Wo = (int)Wo; g.HoWo = (int)(Ho * Wo);
-    g.sh = stride; g.sw = stride; g.ph = pad; g.pw = pad; g.dh = g.dw = 1;
-    g.kstride = H * W; g.img_stride = Cin * H * W;
-    return run_rows(lut, x_dev, w_dev, acc_dev, g, (hipStream_t)stream);
+    return convt_any(lut, x_dev, w_dev, acc_dev, N, Cin, H, W, Cout, kh, kw, stride, pad, (hipStream_t)stream);
 }
 
 
@@ -589,6 +747,7 @@ static int weights_pack(adapt_weights **out, const adapt_lut *lut, const int8_t 
     h->N = N; h->Cin = Cin; h->kh = kh; h->kw = kw; h->Cp = q.Cp; h->Cc = q.Cc; h->n_tiles = q.n_tiles;
     h->dt_bytes = q.dt_bytes;
     h->dt_dev[0] = h->dt_dev[1] = nullptr;
+    h->stride = 1; h->phased = false; h->zsum_dev = nullptr; h->w8_dev = nullptr; h->lut = nullptr;
     for (int half = 0; half <= lut->storage; ++half) {
         hipError_t e = hipMalloc((void **)&h->dt_dev[half], q.dt_bytes);
         if (e != hipSuccess) {
@@ -635,12 +794,84 @@ int adapt_weights_pack_conv2d(adapt_weights **out, const adapt_lut *lut, const i
     return weights_pack(out, lut, w_dev, 1, Cout, Cin, kh, kw, stream, "adapt_weights_pack_conv2d");
 }
 
+int adapt_weights_pack_conv_transpose2d(adapt_weights **out, const adapt_lut *lut, const int8_t *w_dev, int Cin, int Cout, int kh,
+                                        int kw, int stride, void *stream) {
+    const char *who = "adapt_weights_pack_conv_transpose2d";
+    if (!out) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: out is NULL", who);
+    *out = nullptr;
+    int rc = check_lut(lut, who);
+    if (rc) return rc;
+    if (Cout < 1 || Cin < 1 || kh < 1 || kw < 1 || stride < 1) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
+    if (!w_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: w_dev is NULL", who);
+    if ((long long)Cout * Cin * kh * kw > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "%s: more than 2^31-1 weights", who);
+    adapt_weights *h = new (std::nothrow) adapt_weights();
+    if (!h) return fail(ADAPT_ERR_OUT_OF_MEMORY, "%s: host allocation failed", who);
+    h->kind = 2; h->bits = lut->bits; h->storage = lut->storage; h->device = lut->device;
+    h->N = Cout; h->Cin = Cin; h->kh = kh; h->kw = kw; h->stride = stride;
+    h->Cp = h->Cc = h->n_tiles = 0; h->dt_bytes = 0;
+    h->dt_dev[0] = h->dt_dev[1] = nullptr;
+    h->zsum_dev = nullptr; h->w8_dev = nullptr; h->lut = lut;
+    h->phased = kh % stride == 0 && kw % stride == 0 && stride <= 8;
+    const size_t wbytes = (size_t)Cout * Cin * kh * kw;
+    hipError_t e = hipMalloc((void **)&h->w8_dev, wbytes);
+    if (e == hipSuccess) e = hipMemcpyAsync(h->w8_dev, w_dev, wbytes, hipMemcpyDeviceToDevice, (hipStream_t)stream);
+    if (e == hipSuccess && h->phased) {
+        const LinesShape q = convt_phase_shape(lut->bits, Cout, Cin, kh, kw, stride);
+        const size_t all = q.dt_bytes * stride * stride;
+        if (all * (size_t)(lut->storage + 1) > ((size_t)64 << 30)) {
+            h->phased = false;      // too large to hold: this handle keeps to the plain form
+        } else {
+            h->Cp = q.Cp; h->Cc = q.Cc; h->n_tiles = q.n_tiles; h->dt_bytes = all;
+            e = hipMalloc((void **)&h->zsum_dev, (size_t)Cout * kh * kw * sizeof(int32_t));
+            for (int half = 0; half <= lut->storage && e == hipSuccess; ++half) e = hipMalloc((void **)&h->dt_dev[half], all);
+            if (e == hipSuccess) {
+                rc = pack_convt(lut, w_dev, q, kh, kw, stride, h->dt_dev, h->zsum_dev, (hipStream_t)stream);
+                if (rc != ADAPT_OK) {
+                    adapt_weights_destroy(h);
+                    return rc;
+                }
+            }
+        }
+    }
+    if (e != hipSuccess) {
+        adapt_weights_destroy(h);
+        return fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "%s: %s", who, hipGetErrorString(e));
+    }
+    *out = h;
+    return ADAPT_OK;
+}
+
 int adapt_weights_destroy(adapt_weights *h) {
     if (!h) return ADAPT_OK;
     for (int j = 0; j < 2; ++j)
         if (h->dt_dev[j]) (void)hipFree(h->dt_dev[j]);
+    if (h->zsum_dev) (void)hipFree(h->zsum_dev);
+    if (h->w8_dev) (void)hipFree(h->w8_dev);
     delete h;
     return ADAPT_OK;
+}
+
+int adapt_approx_conv_transpose2d_packed(const adapt_weights *h, const int8_t *x_dev, int32_t *acc_dev, int N, int H, int W, int pad,
+                                         void *stream) {
+    const char *who = "adapt_approx_conv_transpose2d_packed";
+    int rc = check_weights(h, 2, who);
+    if (rc) return rc;
+    if (N < 0 || H < 1 || W < 1 || pad < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
+    const long long Ho = ((long long)H - 1) * h->stride - 2LL * pad + h->kh, Wo = ((long long)W - 1) * h->stride - 2LL * pad + h->kw;
+    if (Ho < 1 || Wo < 1) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: empty output", who);
+    if (N == 0) return ADAPT_OK;
+    if (!x_dev || !acc_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
+    if ((long long)N * h->N * Ho * Wo > 0x7fffffffLL || (long long)N * h->Cin * H * W > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
+    if (h->phased && convt_phases_ok(H, W, h->kh, h->kw, h->stride, pad)) {
+        LinesShape q = convt_phase_shape(h->bits, h->N, h->Cin, h->kh, h->kw, h->stride);
+        const long long xt_bytes = (long long)N * (H + 2LL * (q.kh - 1)) * (W + 2LL * (q.kw - 1)) * q.Cp;
+        if (xt_bytes < 0x7fffff00LL)
+            return lines_conv_transpose2d(h->bits, h->storage, q, h->dt_dev, h->zsum_dev, x_dev, acc_dev, N, H, W, h->kh, h->kw,
+                                          h->stride, pad, (hipStream_t)stream);
+    }
+    // geometries outside the phase form (a single input pixel, output sizes that are no multiple of the stride)
+    return convt_rows(h->lut, x_dev, h->w8_dev, acc_dev, N, h->Cin, H, W, h->N, h->kh, h->kw, h->stride, pad, (hipStream_t)stream);
 }
 
 int adapt_approx_linear_packed(const adapt_weights *h, const int8_t *a_dev, int32_t *acc_dev, int M, void *stream) {

@@ -49,7 +49,23 @@ struct LinesParams {
     int ky_stride, kx_stride;   // bytes of xt per filter row / column (dilation * padded width * Cp, dilation * Cp)
     int shift;              // < 0: out = acc; >= 0: out += acc << shift
     int ch_stride;          // x-major activation copy only: bytes per channel step (padded width); else unused
+    // Where row (img, a, b) of the M x N product goes: out[(img * N + n) * out_plane + out_off + a * out_sy + b * out_sx],
+    // (a, b) = position in the HoWo / Wo grid.  Convolution: out_plane = HoWo, out_sy = Wo, out_sx = 1.
+    int out_plane, out_sy, out_sx;
+    // A transposed convolution with stride s is s * s ordinary stride-1 convolutions ("phases"), each with its own
+    // derived tables, window origin in xt and interleaved output positions; up to 4 of them share one launch.
+    // Workgroup order: n-tile fastest, then row tile, then phase.
+    int phases, m_tiles;
+    int xt_off[4];          // bytes into xt
+    int out_off[4];         // elements into an output plane
+    long long dt_off[4];    // 16-byte units into dt
 };
+
+// per-phase launch parameters without indexing the by-value argument block dynamically
+template <typename T>
+__device__ __forceinline__ T pick4(const T *v, int i) {
+    return i == 0 ? v[0] : (i == 1 ? v[1] : (i == 2 ? v[2] : v[3]));
+}
 
 // NCHW int8 -> zero-padded copy, Cp (a multiple of 8) channels per pixel, in one of two orders:
 //   xmajor == 0: channel-last            [N][H + 2 ph][W + 2 pw][Cp]
@@ -124,6 +140,110 @@ __global__ void pack_line_tables_kernel(const uint16_t *__restrict__ lut16, cons
             e[c] = v;
         }
         dt[i] = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+    }
+}
+
+// Derived tables of the s * s phases of a transposed convolution with stride s (kh and kw multiples of s).
+// Output rows with (oy + pad) % s == ry only meet the filter rows ky = ry + s m, m = 0..Ty-1 (Ty = kh / s), and
+// input rows iy = (oy + pad) / s - m: an ordinary stride-1 convolution over the input whose window row m'
+// (top to bottom) carries filter row ky = ry + s (Ty - 1 - m'); likewise for columns.
+// w is [Cin][Cout][kh][kw]; layout [phase = ry * s + rx][n_tile][step = (m' * Tx + n') * Cc + t][line][k-sub].
+__global__ void pack_line_tables_convt_kernel(const uint16_t *__restrict__ lut16, const int8_t *__restrict__ w,
+                                              uint4 *__restrict__ dt, int bits, int N, int Cin, int kh, int kw, int s,
+                                              int Cc, int n_tiles) {
+    const int lines = 1 << bits, mask = lines - 1;
+    const int Ty = kh / s, Tx = kw / s;
+    const size_t per_table = (size_t)lines * 8;
+    const size_t steps = (size_t)Ty * Tx * Cc;
+    const size_t per_phase = (size_t)n_tiles * steps * per_table;
+    const size_t total = per_phase * s * s;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int phase = (int)(i / per_phase);
+        const size_t ip = i - (size_t)phase * per_phase;
+        const int ry = phase / s, rx = phase - ry * s;
+        const int j = (int)(ip & 7);
+        const int a = (int)((ip >> 3) & mask);
+        const size_t ts = ip / per_table;
+        const int step = (int)(ts % steps);
+        const int nt = (int)(ts / steps);
+        const int tap = step / Cc, t = step - tap * Cc;
+        const int mw = tap / Tx, nw = tap - mw * Tx;
+        const int ky = ry + s * (Ty - 1 - mw), kx = rx + s * (Tx - 1 - nw);
+        const int ci = j * Cc + t;
+        uint32_t e[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const int n = nt * 8 + c;
+            uint32_t v = 0;
+            if (n < N && ci < Cin) {
+                const size_t wi = (((size_t)ci * N + n) * kh + ky) * kw + kx;
+                v = lut16[(size_t)a * lines + ((int)w[wi] & mask)];
+            }
+            e[c] = v;
+        }
+        dt[i] = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+    }
+}
+
+// zsum[co][ky * kw + kx] = sum over ci of T[0][w[ci][co][ky][kx]] (int32, wrap-around): what one window tap that
+// lies over the zero border of the padded input copy adds to an output of channel co.
+// lut_lo / lut_hi: 16-bit tables [a & mask][w & mask]; lut_hi == nullptr: lut_lo holds signed entries.
+__global__ void convt_zero_sums_kernel(const uint16_t *__restrict__ lut_lo, const uint16_t *__restrict__ lut_hi,
+                                       const int8_t *__restrict__ w, int32_t *__restrict__ zsum, int bits, int N, int Cin,
+                                       int taps) {
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= N * taps) return;
+    const int co = idx / taps, tap = idx - co * taps;
+    const int mask = (1 << bits) - 1;
+    uint32_t sum = 0;
+    for (int ci = 0; ci < Cin; ++ci) {
+        const int wv = (int)w[((size_t)ci * N + co) * taps + tap] & mask;      // row of activation 0 is row 0
+        if (lut_hi) sum += (uint32_t)lut_lo[wv] + ((uint32_t)(int32_t)(int16_t)lut_hi[wv] << 16);
+        else sum += (uint32_t)(int32_t)(int16_t)lut_lo[wv];
+    }
+    zsum[idx] = (int32_t)sum;
+}
+
+// The phase convolutions look up every window tap, also those over the zero border; the transposed convolution is
+// defined over real (input, weight) pairs only, so for every output pixel near the border the sums of the taps without
+// an input pixel are taken off again.  region 0: the first/last Ly output rows (all columns); region 1: the first/last
+// Lx columns of the remaining rows.  One thread per (image, channel, pixel of the region).
+__global__ void convt_border_fix_kernel(int32_t *__restrict__ out, const int32_t *__restrict__ zsum, int planes, int Cout,
+                                        int Ho, int Wo, int H, int W, int kh, int kw, int s, int pad, int Ly, int Lx,
+                                        int region) {
+    const int nrows = 2 * Ly < Ho ? 2 * Ly : Ho;        // rows of region 0
+    const int ncols = 2 * Lx < Wo ? 2 * Lx : Wo;
+    const int rr = region == 0 ? nrows : Ho - nrows;
+    const int rc = region == 0 ? Wo : ncols;
+    const size_t total = (size_t)planes * rr * rc;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int c = (int)(i % rc);
+        const size_t t = i / rc;
+        const int r = (int)(t % rr);
+        const int plane = (int)(t / rr);
+        int oy, ox;
+        if (region == 0) {
+            oy = (nrows == Ho || r < Ly) ? r : Ho - (nrows - r);
+            ox = c;
+        } else {
+            oy = Ly + r;
+            ox = (ncols == Wo || c < Lx) ? c : Wo - (ncols - c);
+        }
+        const int co = plane % Cout;
+        const int qy = (oy + pad) / s, ry = (oy + pad) - qy * s;
+        const int qx = (ox + pad) / s, rx = (ox + pad) - qx * s;
+        uint32_t extra = 0;
+        for (int m = 0; m * s + ry < kh; ++m) {
+            const bool yin = qy - m >= 0 && qy - m < H;
+            for (int n = 0; n * s + rx < kw; ++n) {
+                const bool xin = qx - n >= 0 && qx - n < W;
+                if (!(yin && xin)) extra += (uint32_t)zsum[(size_t)co * kh * kw + (ry + s * m) * kw + (rx + s * n)];
+            }
+        }
+        int32_t *q = out + ((size_t)plane * Ho + oy) * Wo + ox;
+        *q = (int32_t)((uint32_t)*q - extra);
     }
 }
 
@@ -214,11 +334,15 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_kernel(const LinesPar
     const int j = tid & 7;
     const int rs = tid >> 3;
     const int nt = blockIdx.x % p.n_tiles;      // consecutive workgroup ids land on different XCDs:
-    const int mt = blockIdx.x / p.n_tiles;      // n-tile == id mod n_tiles keeps one table stream per XCD L2
+    const int wg = blockIdx.x / p.n_tiles;      // n-tile == id mod n_tiles keeps one table stream per XCD L2
+    const int mt = wg % p.m_tiles;
+    const int ph = wg / p.m_tiles;
+    const int8_t *const xt = p.xt + pick4(p.xt_off, ph);
+    const int out_off = pick4(p.out_off, ph);
     const int lines = 1 << p.bits;
     const int table_u4 = lines * 8;
     const int steps = p.taps * p.Cc;
-    const uint4 *dt = p.dt + (size_t)nt * steps * table_u4;
+    const uint4 *dt = p.dt + pick4(p.dt_off, ph) + (size_t)nt * steps * table_u4;
     // memory operations per table copy issued by this wave (uniform in the wave)
     const int dma_ops = (wave * 64 < table_u4 ? 1 : 0) + (wave * 64 + LINES_THREADS < table_u4 ? 1 : 0);
 
@@ -251,7 +375,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_kernel(const LinesPar
     // registers are passed through that wait so no use can be scheduled ahead of it.
     auto load_acts = [&](uint32_t *aw, int tap, int t4) {
         const int ky = tap / p.kw, kx = tap - ky * p.kw;
-        const int8_t *xrow = p.xt + (ky * p.ky_stride + kx * p.kx_stride) + t4;
+        const int8_t *xrow = xt + (ky * p.ky_stride + kx * p.kx_stride) + t4;
 #pragma unroll
         for (int i = 0; i < R; ++i) {
             if (REGULAR) {
@@ -363,7 +487,8 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_kernel(const LinesPar
 #pragma unroll
                 for (int c = 1; c < 8; ++c) v = (j == c) ? acc[i * 8 + c] : v;
                 const int img = r / p.HoWo, pix = r - img * p.HoWo;
-                int32_t *q = p.out + ((size_t)img * p.N + n) * p.HoWo + pix;
+                const int a = pix / p.Wo, b = pix - a * p.Wo;
+                int32_t *q = p.out + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
                 if (p.shift < 0) *q = (int32_t)v;
                 else *q = (int32_t)((uint32_t)*q + (v << p.shift));
             }
@@ -455,12 +580,16 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     const int j = tid & 7;
     const int rs = tid >> 3;
     const int nt = blockIdx.x % p.n_tiles;
-    const int mt = blockIdx.x / p.n_tiles;
+    const int wg = blockIdx.x / p.n_tiles;
+    const int mt = wg % p.m_tiles;
+    const int ph = wg / p.m_tiles;
+    const int8_t *const xt = p.xt + pick4(p.xt_off, ph);
+    const int out_off = pick4(p.out_off, ph);
     const int lines = 1 << p.bits;
     const int table_u4 = lines * 8;
     const int steps = p.taps * p.Cc;
     const int groups = steps >> 2;
-    const unsigned char *dt = reinterpret_cast<const unsigned char *>(p.dt + (size_t)nt * steps * table_u4);
+    const unsigned char *dt = reinterpret_cast<const unsigned char *>(p.dt + pick4(p.dt_off, ph) + (size_t)nt * steps * table_u4);
     const uint32_t table_bytes = (uint32_t)table_u4 * 16u;
 
     // table copy geometry: 8-bit tables take two operations of 64 lanes per wave, smaller tables one
@@ -548,7 +677,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     u32x4_t aw[AQ], awn[AQ];
 #pragma unroll
     for (int q = 0; q < AQ; ++q) { aw[q] = u32x4_t{0, 0, 0, 0}; awn[q] = u32x4_t{0, 0, 0, 0}; }
-    load_acts(aw, p.xt);
+    load_acts(aw, xt);
     __builtin_amdgcn_s_waitcnt(WAIT_ALL);
     __builtin_amdgcn_s_barrier();
     tie(aw);
@@ -571,7 +700,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
         const bool tail = g >= groups - 2;      // not every operation of the steady-state schedule is issued
         // u = 0: table buffers 0 (this step) and 1 (next step)
         if (s0 + 3 < steps) dma(s0 + 3, 3);
-        if (!last) load_acts(awn, p.xt + tapoff + t4off);
+        if (!last) load_acts(awn, xt + tapoff + t4off);
 #pragma unroll
         for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<0, 0>(rv[i], aw[(H + i) / 4][(H + i) % 4], ubits, cb0); }
 #pragma unroll
@@ -637,16 +766,18 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
 #pragma unroll
                 for (int c = 1; c < 8; ++c) v[i] = (j == c) ? acc[i * 8 + c] : v[i];
             }
-            int32_t *q0 = p.out + ((size_t)img0 * p.N + n) * p.HoWo + pix0;
+            const int a0 = pix0 / p.Wo, b0 = pix0 - a0 * p.Wo;
+            int32_t *q0 = p.out + ((size_t)img0 * p.N + n) * p.out_plane + out_off + a0 * p.out_sy + b0 * p.out_sx;
             if (r0 + 8 <= p.M) {
-                if (p.shift < 0 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {       // two 16-byte stores
+                if (p.shift < 0 && p.out_sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {       // two 16-byte stores
                     reinterpret_cast<uint4 *>(q0)[0] = make_uint4(v[0], v[1], v[2], v[3]);
                     reinterpret_cast<uint4 *>(q0)[1] = make_uint4(v[4], v[5], v[6], v[7]);
                 } else {
+                    const int sx = p.out_sx;
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
-                        if (p.shift < 0) q0[i] = (int32_t)v[i];
-                        else q0[i] = (int32_t)((uint32_t)q0[i] + (v[i] << p.shift));
+                        if (p.shift < 0) q0[i * sx] = (int32_t)v[i];
+                        else q0[i * sx] = (int32_t)((uint32_t)q0[i * sx] + (v[i] << p.shift));
                     }
                 }
             }
@@ -661,7 +792,8 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
                     int img, pix;
                     if (REGULAR && p.HoWo > 1) { img = img0; pix = pix0 + i; }      // R consecutive pixels of one output row
                     else { img = r / p.HoWo; pix = r - img * p.HoWo; }
-                    int32_t *q = p.out + ((size_t)img * p.N + n) * p.HoWo + pix;
+                    const int a = pix / p.Wo, b = pix - a * p.Wo;
+                    int32_t *q = p.out + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
                     if (p.shift < 0) *q = (int32_t)v;
                     else *q = (int32_t)((uint32_t)*q + (v << p.shift));
                 }

@@ -41,6 +41,8 @@ class ResNet20:
         self.lut = B.Lut(cfg["lut"], self.bits)
         self.plan = resnet20_plan()
         self.qws = [quantize_weights(torch.from_numpy(w).to(device), self.bits) for w in cfg["convs"]]
+        # the weights are static: combine them with the table once (Sec. III-B / III-C)
+        self.pws = [B.adapt_weights_pack_conv2d(self.lut, qw) for qw, _ in self.qws]
         self.qfw, self.s_fw = quantize_weights(torch.from_numpy(cfg["fc_w"]).to(device), self.bits)
         self.fc_b = torch.from_numpy(cfg["fc_b"]).to(device)
         self.scales = None
@@ -52,7 +54,7 @@ class ResNet20:
         used.append(s_x)
         qx = B.adapt_quantize_f32(x, s_x, bits)
         st = self.plan[i][2]
-        acc = B.adapt_approx_conv2d(self.lut, qx, self.qws[i][0], (st, st), (1, 1))
+        acc = B.adapt_approx_conv2d_packed(self.pws[i], qx, (st, st), (1, 1))
         if keep is not None:
             keep.append(acc)
         n, c, h, w = acc.shape
@@ -87,6 +89,7 @@ class LSTM:
         self.lut = B.Lut(cfg["lut"], self.bits)
         self.q_wih, self.s_wih = quantize_weights(torch.from_numpy(cfg["w_ih"]).to(device), self.bits)
         self.q_whh, self.s_whh = quantize_weights(torch.from_numpy(cfg["w_hh"]).to(device), self.bits)
+        self.p_wih = B.adapt_weights_pack_linear(self.lut, self.q_wih)      # one long product over all time steps
         self.bias = torch.from_numpy(cfg["bias"]).to(device)
         self.Hs = cfg["w_hh"].shape[1]
         self.s_x = None
@@ -99,7 +102,7 @@ class LSTM:
             self.s_x = calibrated_scale(x, bits)          # over the whole [T, B, I] input
         s_h = _f(1.0) / _f(Q)
         qx = B.adapt_quantize_f32(x, self.s_x, bits).view(T * Bn, I)
-        acc_ih = B.adapt_approx_linear(self.lut, qx, self.q_wih).view(T, Bn, 4 * self.Hs)
+        acc_ih = B.adapt_approx_linear_packed(self.p_wih, qx).view(T, Bn, 4 * self.Hs)
         hs = torch.empty((T, Bn, self.Hs), dtype=torch.float32, device=x.device)
         h = torch.zeros((Bn, self.Hs), dtype=torch.float32, device=x.device)
         c = torch.zeros((Bn, self.Hs), dtype=torch.float32, device=x.device)
@@ -121,6 +124,7 @@ class DCGAN:
         self.lut = B.Lut(cfg["lut"], self.bits)
         self.plan = cfg["plan"]
         self.qws = [quantize_weights(torch.from_numpy(w).to(device), self.bits) for w in cfg["ws"]]
+        self.pws = [B.adapt_weights_pack_conv_transpose2d(self.lut, qw, s) for (qw, _), (_, _, s, _) in zip(self.qws, self.plan)]
         self.scales = None
 
     def forward(self, z, keep=None):
@@ -132,7 +136,7 @@ class DCGAN:
             s_x = calibrated_scale(x, self.bits) if self.scales is None else self.scales[i]
             used.append(s_x)
             qx = B.adapt_quantize_f32(x, s_x, self.bits)
-            acc = B.adapt_approx_conv_transpose2d(self.lut, qx, self.qws[i][0], s, p)
+            acc = B.adapt_approx_conv_transpose2d_packed(self.pws[i], qx, p)
             if keep is not None:
                 keep.append(acc)
             n, c, h, w = acc.shape

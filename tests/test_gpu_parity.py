@@ -453,3 +453,68 @@ def test_packed_handle_errors(B):
     out = torch.zeros((1, 4, 5, 5), dtype=torch.int32, device="cuda")
     rc = B.load().adapt_approx_conv2d_packed(pw.handle, x.data_ptr(), out.data_ptr(), 1, 5, 5, 1, 1, 0, 0, 1, 1, None)
     assert rc == -1          # linear handle used for a convolution
+
+
+# ------------------------------------------------------------------ transposed convolution, packed (phase form)
+
+PACKED_CONVT = [
+    # N, Cin, H, W, Cout, k, stride, pad
+    (2, 8, 4, 4, 8, 4, 2, 1),          # generator geometry, 4 rows per image row (irregular rows)
+    (3, 32, 8, 8, 16, 4, 2, 1),        # 8 regular rows per lane, fast kernel
+    (2, 64, 16, 16, 24, 4, 2, 1),      # x-major activation copy
+    (40, 32, 8, 8, 8, 4, 2, 1),
+    (2, 5, 7, 5, 3, 4, 2, 1),          # ragged everything
+    (1, 6, 5, 6, 4, 3, 1, 1),          # stride 1: one phase, borders on all sides
+    (2, 4, 6, 6, 3, 3, 1, 0),
+    (2, 4, 6, 6, 3, 3, 1, 2),
+    (2, 7, 5, 5, 5, 2, 2, 0),          # kernel == stride: no overlap, no border terms
+    (1, 4, 6, 4, 2, 4, 2, 0),
+    (2, 4, 5, 5, 2, 4, 2, 2),          # crop wider than the border
+    (1, 3, 4, 4, 2, 6, 2, 1),          # three taps per phase
+    (1, 3, 4, 5, 2, 3, 3, 0),          # nine phases: more than one launch
+    (1, 4, 4, 4, 2, 6, 3, 3),
+    (2, 3, 5, 3, 2, 3, 2, 0),          # kernel no multiple of the stride: plain form inside the handle
+    (1, 2, 4, 4, 2, 5, 3, 2),
+    (4, 10, 1, 1, 6, 4, 1, 0),         # a single input pixel
+    (3, 5, 1, 1, 2, 4, 2, 1),
+    (300, 16, 4, 4, 8, 4, 2, 1),
+]
+
+
+@pytest.mark.parametrize("bits", [6, 8])
+@pytest.mark.parametrize("case", PACKED_CONVT)
+def test_conv_transpose2d_packed_bit_exact(B, bits, case):
+    N, Cin, H, W, Cout, k, s, p = case
+    rng = np.random.default_rng(bits + 31 * sum(case))
+    x = wl.random_i8(rng, (N, Cin, H, W), bits, "gauss")
+    w = wl.random_i8(rng, (Cin, Cout, k, k), bits, "gauss")
+    lut = wl.make_lut(bits)
+    L = B.Lut(lut, bits)
+    want = orc.approx_conv_transpose2d(lut, bits, x, w, s, p, threads=8)
+    pk = B.adapt_weights_pack_conv_transpose2d(L, dev(w), s)
+    got = host(B.adapt_approx_conv_transpose2d_packed(pk, dev(x), p))
+    assert got.shape == want.shape and (got == want).all()
+    assert (host(B.adapt_approx_conv_transpose2d(L, dev(x), dev(w), s, p)) == want).all()
+
+
+def test_conv_transpose2d_packed_rect_kernel_and_wide_table(B):
+    # entries beyond int16 (two table halves) and a constant table: counts real pairs only
+    rng = np.random.default_rng(77)
+    bits = 5
+    lut = rng.integers(-3_000_000, 3_000_000, size=(32, 32)).astype(np.int32)
+    x = wl.random_i8(rng, (3, 9, 6, 8), bits)
+    w = wl.random_i8(rng, (9, 5, 4, 4), bits)
+    L = B.Lut(lut, bits)
+    pk = B.adapt_weights_pack_conv_transpose2d(L, dev(w), 2)
+    want = orc.approx_conv_transpose2d(lut, bits, x, w, 2, 1, threads=4)
+    assert (host(B.adapt_approx_conv_transpose2d_packed(pk, dev(x), 1)) == want).all()
+    t = np.full((16, 16), 3, dtype=np.int32)
+    x = wl.random_i8(rng, (2, 4, 5, 5), 4)
+    w = wl.random_i8(rng, (4, 3, 4, 4), 4)
+    pk = B.adapt_weights_pack_conv_transpose2d(B.Lut(t, 4), dev(w), 2)
+    got = host(B.adapt_approx_conv_transpose2d_packed(pk, dev(x), 1))
+    # stride 2, kernel 4, pad 1: interior outputs meet 2 x 2 taps, edges 1 x 2, corners 1 x 1
+    cnt = np.full((10, 10), 4)
+    cnt[0, :] = cnt[-1, :] = cnt[:, 0] = cnt[:, -1] = 2
+    cnt[0, 0] = cnt[0, -1] = cnt[-1, 0] = cnt[-1, -1] = 1
+    assert (got == (3 * 4 * cnt)[None, None]).all()
