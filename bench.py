@@ -36,7 +36,16 @@ def _f(x):
     return np.float32(x)
 
 
-def build_step(cfg_id, bits, torch, B, gnet, wl):
+def _graph_step(gnet, net, x, eager):
+    """The network configurations are chains of many small launches: one step = one replay of the forward pass recorded
+    into a HIP graph (same kernels, same order); --eager launches them one by one instead."""
+    if eager:
+        return lambda: net.forward(x)
+    cap = gnet.Captured(net, x)
+    return lambda: cap.replay()
+
+
+def build_step(cfg_id, bits, torch, B, gnet, wl, eager=False):
     """Returns (step_fn, core_fn, macs, workload_name, dtype) for a configuration.
     step_fn(): one pass of the whole path; core_fn(): only the dominant table-lookup call."""
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
@@ -81,27 +90,21 @@ def build_step(cfg_id, bits, torch, B, gnet, wl):
         net = gnet.ResNet20(c)
         x = dev(c["x"])
         net.forward(x)            # calibration pass (host reads), scales frozen afterwards
-
-        def step():
-            net.forward(x)
+        step = _graph_step(gnet, net, x, eager)
         return step, None, gnet.lut_macs_resnet20(128), "config3: ResNet-20-style CNN, batch 128, 8-bit table", net
     if cfg_id == 4:
         c = wl.config4()
         net = gnet.LSTM(c)
         x = dev(c["x"])
         net.forward(x)
-
-        def step():
-            net.forward(x)
+        step = _graph_step(gnet, net, x, eager)
         return step, None, gnet.lut_macs_lstm(100, 64, 512, 512), "config4: LSTM 512/512, seq 100, batch 64, 7-bit table", net
     if cfg_id == 5:
         c = wl.config5(bits=bits)
         net = gnet.DCGAN(c)
         z = dev(c["z"])
         net.forward(z)
-
-        def step():
-            net.forward(z)
+        step = _graph_step(gnet, net, z, eager)
         return step, None, gnet.lut_macs_dcgan(256, c["plan"]), f"config5: DCGAN-style generator, batch 256, {bits}-bit table", net
     raise SystemExit(f"unknown config {cfg_id}")
 
@@ -164,6 +167,7 @@ def main():
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--bits", type=int, default=8, help="table bits for config 5 (6 or 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eager", action="store_true", help="network configurations: launch kernel by kernel instead of replaying a HIP graph")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run three plain 64 MiB device-to-device copies (what FETCH_SIZE / WRITE_SIZE are scaled by)")
     ap.add_argument("--traffic-bytes", type=float, default=None,
@@ -187,7 +191,7 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes": 64 << 20, "copies": 3}))
         return
-    step, core, macs, name, _keep = build_step(args.config, args.bits, torch, B, gnet, wl)
+    step, core, macs, name, _keep = build_step(args.config, args.bits, torch, B, gnet, wl, args.eager)
 
     for _ in range(args.warmup):
         step()

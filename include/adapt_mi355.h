@@ -26,8 +26,12 @@
  *   - Output buffers are overwritten, never accumulated into.
  *   - Handles (adapt_lut) own their device memory and belong to the device that
  *     was current when they were created.
- *   - Two calls that overlap in time on different streams are safe; workspaces
- *     are allocated per call in stream order.
+ *   - Two calls that overlap in time on different streams are safe for the plain
+ *     entry points (workspaces are allocated per call in stream order).  A packed
+ *     weights handle owns a grow-only workspace: calls with the SAME handle must not
+ *     overlap in time; once a handle has run at its largest input size its calls
+ *     allocate nothing and may be recorded into a HIP graph (which a later call
+ *     at a larger size, re-allocating the workspace, would invalidate).
  */
 #ifndef ADAPT_MI355_H
 #define ADAPT_MI355_H
@@ -121,7 +125,8 @@ int adapt_approx_conv_transpose2d(const adapt_lut *lut, const int8_t *x_dev, con
  * T[a][w[n][k]] for all activations a, in the order the long-matrix kernel streams them.  The handle
  * owns K * N * 2^b * 2 bytes of device memory (twice that for tables with entries beyond int16) and
  * is tied to the device, the table contents and the weight values at pack time; w_dev may be freed
- * once the stream has passed the call.  The packed entry points give the same integers as the plain
+ * once the stream has passed the call.  The handle keeps a pointer to `lut`: the table handle must stay alive as long
+ * as the weights handle is used (short linear layers run on the whole-table kernel with pre-packed row offsets).  The packed entry points give the same integers as the plain
  * ones; they skip the per-call packing that the plain entry points do for long matrices.
  * ---------------------------------------------------------------------------------------------- */
 typedef struct adapt_weights adapt_weights;
@@ -176,6 +181,12 @@ int adapt_sigmoid_f32(const float *x_dev, float *y_dev, size_t n, void *stream);
  * acc_ih_dev, acc_hh_dev [B][4 Hs] int32; c_dev [B][Hs] updated in place; h_dev [B][Hs] written. */
 int adapt_lstm_cell_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh,
                         const float *bias_dev, float *c_dev, float *h_dev, int B, int Hs, void *stream);
+
+/* The same cell, and in the same kernel the next step's operand: qh = quantise(h, s_h, bits) exactly as
+ * adapt_quantize_f32 would (Sec. III-A); qh_dev [B][Hs] int8. */
+int adapt_lstm_cell_q_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh,
+                          const float *bias_dev, float *c_dev, float *h_dev, int8_t *qh_dev, float s_h, int bits, int B,
+                          int Hs, void *stream);
 
 #ifdef __cplusplus
 }

@@ -28,7 +28,7 @@ EXPORTS = [
     "adapt_weights_destroy",
     "adapt_approx_linear_packed", "adapt_approx_conv2d_packed", "adapt_approx_conv_transpose2d_packed",
     "adapt_relu_f32", "adapt_add_f32", "adapt_avgpool_hw_f32", "adapt_shortcut_a_f32",
-    "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32",
+    "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32", "adapt_lstm_cell_q_f32",
 ]
 
 
@@ -78,6 +78,7 @@ def load() -> ctypes.CDLL:
     L.adapt_tanh_f32.argtypes = [vp, vp, sz, vp]
     L.adapt_sigmoid_f32.argtypes = [vp, vp, sz, vp]
     L.adapt_lstm_cell_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, i32, i32, vp]
+    L.adapt_lstm_cell_q_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, vp, f32, i32, i32, i32, vp]
     for name in EXPORTS:
         if name != "adapt_last_error":
             getattr(L, name).restype = i32
@@ -355,3 +356,12 @@ def adapt_lstm_cell_f32(acc_ih, acc_hh, s_ih: float, s_hh: float, bias, c, h, st
                                     _ptr(bias, torch.float32), _ptr(c, torch.float32), _ptr(h, torch.float32), B, Hs,
                                     _stream(stream)))
     return h, c
+
+
+def adapt_lstm_cell_q_f32(acc_ih, acc_hh, s_ih: float, s_hh: float, bias, c, h, qh, s_h: float, bits: int, stream=None):
+    B, H4 = acc_ih.shape
+    Hs = H4 // 4
+    _chk(load().adapt_lstm_cell_q_f32(_ptr(acc_ih, torch.int32), _ptr(acc_hh, torch.int32), float(s_ih), float(s_hh),
+                                      _ptr(bias, torch.float32), _ptr(c, torch.float32), _ptr(h, torch.float32),
+                                      _ptr(qh, torch.int8), float(s_h), bits, B, Hs, _stream(stream)))
+    return h, c, qh

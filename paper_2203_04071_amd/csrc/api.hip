@@ -42,6 +42,37 @@ inline unsigned ew_grid(size_t work_items) {
     return (unsigned)g;
 }
 
+// Scratch memory of one call.  Plain entry points take it from the stream-ordered allocator and give it back in stream
+// order; a packed-weights handle keeps one grow-only buffer, so that its calls allocate nothing once they have run at
+// their largest size (they can then be recorded into a HIP graph).
+struct Workspace {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+};
+
+int ws_get(Workspace *cache, size_t bytes, hipStream_t s, void **out) {
+    if (!cache) {
+        HIP_TRY(hipMallocAsync(out, bytes, s));
+        return ADAPT_OK;
+    }
+    if (cache->bytes < bytes) {
+        if (cache->ptr) HIP_TRY(hipFree(cache->ptr));       // waits for the device: no earlier call still uses it
+        cache->ptr = nullptr;
+        cache->bytes = 0;
+        HIP_TRY(hipMalloc(&cache->ptr, bytes));
+        cache->bytes = bytes;
+    }
+    *out = cache->ptr;
+    return ADAPT_OK;
+}
+
+int ws_put(Workspace *cache, void *p, hipStream_t s, int rc) {
+    if (cache || !p) return rc;
+    hipError_t fe = hipFreeAsync(p, s);
+    if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
+    return rc;
+}
+
 }  // namespace
 
 struct adapt_lut {
@@ -68,6 +99,14 @@ struct adapt_weights {
     int32_t *zsum_dev;      // [Cout][kh * kw] sums of T[0][w] over the input channels
     int8_t *w8_dev;         // copy of the weights for the geometries the phase form does not cover
     const adapt_lut *lut;   // the table handle (must outlive this handle), for those geometries
+    mutable Workspace ws;   // padded activation copy of the latest call
+    // linear layers only: row offsets [K][wofs_npad] for the whole-table kernel, which serves short activation matrices
+    // transposed convolutions: the same for the gather form (wofs_dev, [kh kw Cin][wofs_npad]) and for the single-pixel
+    // form, a linear layer with Cout kh kw outputs (wofs1_dev, [Cin][wofs1_npad])
+    uint32_t *wofs_dev;
+    int wofs_npad;
+    uint32_t *wofs1_dev;
+    int wofs1_npad;
 };
 
 extern "C" {
@@ -227,7 +266,10 @@ struct Geometry {
 };
 
 // Run the rows kernel once per table image of the handle.
-int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *out, const Geometry &g, hipStream_t s) {
+// prepacked: row offsets [K][prepacked_npad] made earlier by pack_row_offsets_kernel (prepacked_npad a multiple of 16),
+// or nullptr to pack `w` into a stream-ordered temporary.
+int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *out, const Geometry &g, hipStream_t s,
+             const uint32_t *prepacked = nullptr, int prepacked_npad = 0) {
     const int bits = lut->bits;
     const long long Ktot = (long long)g.taps * g.Cin;
     if (g.M == 0 || g.N == 0) return ADAPT_OK;
@@ -248,20 +290,22 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     while (MT > 64 && (MT / 2 >= g.M || (groups(NT, MT) < cu && Ktot / (adapt::ROWS_THREADS / (MT / 2)) >= 16))) MT /= 2;
     if (groups(NT, MT) < cu && g.N > 8) NT = 8;
     const int KS = adapt::ROWS_THREADS / MT;
-    const int Npad = ((g.N + NT - 1) / NT) * NT;
+    const int Npad = prepacked ? prepacked_npad : ((g.N + NT - 1) / NT) * NT;
 
     uint32_t *wofs = nullptr;
-    HIP_TRY(hipMallocAsync((void **)&wofs, (size_t)Ktot * Npad * sizeof(uint32_t), s));
-    const size_t pack_n = (size_t)Ktot * Npad;
-    adapt::pack_row_offsets_kernel<<<(unsigned)((pack_n + 255) / 256), 256, 0, s>>>(
-        w, wofs, (int)Ktot, g.N, Npad, g.Cin, g.taps, g.wt ? (int)adapt::MODE_CONVT : g.mode, 1 << (bits - 1), (1 << bits) - 1,
-        lut->rs * 2);
-    hipError_t pe = hipGetLastError();
     int rc = ADAPT_OK;
-    if (pe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "pack_row_offsets launch: %s", hipGetErrorString(pe));
+    if (!prepacked) {
+        HIP_TRY(hipMallocAsync((void **)&wofs, (size_t)Ktot * Npad * sizeof(uint32_t), s));
+        const size_t pack_n = (size_t)Ktot * Npad;
+        adapt::pack_row_offsets_kernel<<<(unsigned)((pack_n + 255) / 256), 256, 0, s>>>(
+            w, wofs, (int)Ktot, g.N, Npad, g.Cin, g.taps, g.wt ? (int)adapt::MODE_CONVT : g.mode, 1 << (bits - 1), (1 << bits) - 1,
+            lut->rs * 2);
+        hipError_t pe = hipGetLastError();
+        if (pe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "pack_row_offsets launch: %s", hipGetErrorString(pe));
+    }
 
     adapt::RowsParams p;
-    p.x = x; p.wofs = wofs; p.out = out;
+    p.x = x; p.wofs = prepacked ? prepacked : wofs; p.out = out;
     p.img_bytes = lut->img_bytes;
     p.M = g.M; p.N = g.N; p.Npad = Npad; p.mode = g.mode; p.Cin = g.Cin; p.taps = g.taps; p.kw = g.kw;
     p.H = g.H; p.W = g.W; p.Wo = g.Wo; p.HoWo = g.HoWo;
@@ -280,8 +324,10 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
         if (NT == 16) rc = sgn ? launch_rows_inst<16, true>(p, grid, lds, s) : launch_rows_inst<16, false>(p, grid, lds, s);
         else rc = sgn ? launch_rows_inst<8, true>(p, grid, lds, s) : launch_rows_inst<8, false>(p, grid, lds, s);
     }
-    hipError_t fe = hipFreeAsync(wofs, s);
-    if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
+    if (wofs) {
+        hipError_t fe = hipFreeAsync(wofs, s);
+        if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
+    }
     return rc;
 }
 
@@ -420,12 +466,14 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
 }
 
 // activation side of a linear layer: A itself when its rows are a multiple of 32 bytes, else a zero-padded copy
-int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *a, int32_t *out, int M, hipStream_t s) {
+int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *a, int32_t *out, int M, hipStream_t s,
+                 Workspace *ws) {
     const int K = q.Cin, Kp = q.Cp;
     int8_t *tmp = nullptr;
     const int8_t *xt = a;
     if (Kp != K) {
-        HIP_TRY(hipMallocAsync((void **)&tmp, (size_t)M * Kp + 16, s));
+        int wrc = ws_get(ws, (size_t)M * Kp + 16, s, (void **)&tmp);
+        if (wrc) return wrc;
         const size_t total = (size_t)M * Kp;
         size_t blocks = (total + 255) / 256;
         if (blocks > 65536) blocks = 65536;
@@ -439,16 +487,12 @@ int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     c.out_plane = 1; c.out_sy = 0; c.out_sx = 0;
     c.phases.resize(1);
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s);
-    if (tmp) {
-        hipError_t fe = hipFreeAsync(tmp, s);
-        if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
-    }
-    return rc;
+    return ws_put(ws, tmp, s, rc);
 }
 
 // activation side of a convolution: zero-padded channel-last copy of x
 int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *x, int32_t *out, int N, int H,
-                 int W, int Ho, int Wo, int sh, int sw, int ph, int pw, int dh, int dw, hipStream_t s) {
+                 int W, int Ho, int Wo, int sh, int sw, int ph, int pw, int dh, int dw, hipStream_t s, Workspace *ws) {
     const int Hp = H + 2 * ph, Wp = W + 2 * pw, Cp = q.Cp;
     const size_t xt_bytes = (size_t)N * Hp * Wp * Cp;
     // With 8 rows per lane that are 8 consecutive output pixels of a stride-1 convolution, the copy is laid
@@ -456,8 +500,9 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     const int M = N * Ho * Wo;
     const int xmajor = (lines_rows_per_lane(M, q.n_tiles) == 8 && Wo % 8 == 0 && sw == 1 && q.Cc % 4 == 0) ? 1 : 0;
     int8_t *xt = nullptr;
-    HIP_TRY(hipMallocAsync((void **)&xt, xt_bytes + 64, s));
     {
+        int wrc = ws_get(ws, xt_bytes + 64, s, (void **)&xt);
+        if (wrc) return wrc;
         const size_t total = xt_bytes / 4;
         size_t blocks = (total + 255) / 256;
         if (blocks > 65536) blocks = 65536;
@@ -473,9 +518,7 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     c.out_plane = Ho * Wo; c.out_sy = Wo; c.out_sx = 1;
     c.phases.resize(1);
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s);
-    hipError_t fe = hipFreeAsync(xt, s);
-    if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
-    return rc;
+    return ws_put(ws, xt, s, rc);
 }
 
 // Transposed convolution as stride * stride stride-1 convolutions (see pack_line_tables_convt_kernel).  Needs kernel
@@ -489,7 +532,7 @@ LinesShape convt_phase_shape(int bits, int Cout, int Cin, int kh, int kw, int st
 }
 
 int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int32_t *zsum, const int8_t *x,
-                           int32_t *out, int N, int H, int W, int kh, int kw, int st, int pad, hipStream_t s) {
+                           int32_t *out, int N, int H, int W, int kh, int kw, int st, int pad, hipStream_t s, Workspace *ws) {
     const int Ty = q.kh, Tx = q.kw, Cp = q.Cp;
     const int Hp = H + 2 * (Ty - 1), Wp = W + 2 * (Tx - 1);
     const int Ho = (H - 1) * st - 2 * pad + kh, Wo = (W - 1) * st - 2 * pad + kw;
@@ -498,8 +541,9 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
     const size_t xt_bytes = (size_t)N * Hp * Wp * Cp;
     const int xmajor = (lines_rows_per_lane(M, q.n_tiles * st * st) == 8 && Qx % 8 == 0 && q.Cc % 4 == 0) ? 1 : 0;
     int8_t *xt = nullptr;
-    HIP_TRY(hipMallocAsync((void **)&xt, xt_bytes + 64, s));
     {
+        int wrc = ws_get(ws, xt_bytes + 64, s, (void **)&xt);
+        if (wrc) return wrc;
         const size_t total = xt_bytes / 4;
         size_t blocks = (total + 255) / 256;
         if (blocks > 65536) blocks = 65536;
@@ -525,8 +569,7 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
             c.phases.push_back(f);
         }
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s);
-    hipError_t fe = hipFreeAsync(xt, s);
-    if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
+    rc = ws_put(ws, xt, s, rc);
     if (rc != ADAPT_OK) return rc;
     // window taps over the zero border were looked up; the layer is defined over real pairs only
     const int Ly = kh - st - pad > 0 ? kh - st - pad : 0, Lx = kw - st - pad > 0 ? kw - st - pad : 0;
@@ -600,7 +643,7 @@ int check_lut(const adapt_lut *lut, const char *who) {
 
 // transposed convolution on the rows kernel
 int convt_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *acc, int N, int Cin, int H, int W, int Cout, int kh,
-               int kw, int stride, int pad, hipStream_t s) {
+               int kw, int stride, int pad, hipStream_t s, const adapt_weights *h = nullptr) {
     const int Ho = (H - 1) * stride - 2 * pad + kh, Wo = (W - 1) * stride - 2 * pad + kw;
     Geometry g{};
     if (H == 1 && W == 1 && pad == 0) {
@@ -609,13 +652,13 @@ int convt_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *
         g.mode = adapt::MODE_GEMM; g.M = N; g.N = Cout * kh * kw; g.Cin = Cin; g.taps = 1; g.kw = 1;
         g.H = 1; g.W = 1; g.Wo = 1; g.HoWo = 1; g.sh = g.sw = g.dh = g.dw = 1; g.ph = g.pw = 0;
         g.kstride = 1; g.img_stride = Cin; g.wt = 1;
-        return run_rows(lut, x, w, acc, g, s);
+        return h ? run_rows(lut, x, w, acc, g, s, h->wofs1_dev, h->wofs1_npad) : run_rows(lut, x, w, acc, g, s);
     }
     g.mode = adapt::MODE_CONVT; g.M = N * Ho * Wo; g.N = Cout; g.Cin = Cin; g.taps = kh * kw; g.kw = kw;
     g.H = H; g.W = W; g.Wo = Wo; g.HoWo = Ho * Wo;
     g.sh = stride; g.sw = stride; g.ph = pad; g.pw = pad; g.dh = g.dw = 1;
     g.kstride = H * W; g.img_stride = Cin * H * W;
-    return run_rows(lut, x, w, acc, g, s);
+    return h ? run_rows(lut, x, w, acc, g, s, h->wofs_dev, h->wofs_npad) : run_rows(lut, x, w, acc, g, s);
 }
 
 // transposed convolution with plain weights: the cheapest form the geometry allows
@@ -636,7 +679,7 @@ int convt_any(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *a
             if (e != hipSuccess)
                 rc = fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "hipMallocAsync(tables): %s", hipGetErrorString(e));
             if (rc == ADAPT_OK) rc = pack_convt(lut, w, q, kh, kw, stride, dt, zsum, s);
-            if (rc == ADAPT_OK) rc = lines_conv_transpose2d(lut->bits, lut->storage, q, dt, zsum, x, acc, N, H, W, kh, kw, stride, pad, s);
+            if (rc == ADAPT_OK) rc = lines_conv_transpose2d(lut->bits, lut->storage, q, dt, zsum, x, acc, N, H, W, kh, kw, stride, pad, s, nullptr);
             for (int half = 0; half < 2; ++half)
                 if (dt[half]) (void)hipFreeAsync(dt[half], s);
             if (zsum) (void)hipFreeAsync(zsum, s);
@@ -667,7 +710,7 @@ int adapt_approx_linear(const adapt_lut *lut, const int8_t *a_dev, const int8_t 
         const LinesShape q = lines_shape(0, lut->bits, N, K, 1, 1);
         if (lines_fits((long long)M * q.Cp, q.dt_bytes, lut->storage))
             return with_temp_tables(lut, w_dev, q, (hipStream_t)stream, [&](uint4 *const dt[2]) {
-                return lines_linear(lut->bits, lut->storage, q, dt, a_dev, acc_dev, M, (hipStream_t)stream);
+                return lines_linear(lut->bits, lut->storage, q, dt, a_dev, acc_dev, M, (hipStream_t)stream, nullptr);
             });
     }
     return run_rows(lut, a_dev, w_dev, acc_dev, g, (hipStream_t)stream);
@@ -703,7 +746,7 @@ int adapt_approx_conv2d(const adapt_lut *lut, const int8_t *x_dev, const int8_t 
         if (lines_fits(xt_bytes, q.dt_bytes, lut->storage))
             return with_temp_tables(lut, w_dev, q, (hipStream_t)stream, [&](uint4 *const dt[2]) {
                 return lines_conv2d(lut->bits, lut->storage, q, dt, x_dev, acc_dev, N, H, W, (int)Ho, (int)Wo, stride_h, stride_w,
-                                    pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream);
+                                    pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream, nullptr);
             });
     }
     return run_rows(lut, x_dev, w_dev, acc_dev, g, (hipStream_t)stream);
@@ -747,22 +790,31 @@ static int weights_pack(adapt_weights **out, const adapt_lut *lut, const int8_t 
     h->N = N; h->Cin = Cin; h->kh = kh; h->kw = kw; h->Cp = q.Cp; h->Cc = q.Cc; h->n_tiles = q.n_tiles;
     h->dt_bytes = q.dt_bytes;
     h->dt_dev[0] = h->dt_dev[1] = nullptr;
-    h->stride = 1; h->phased = false; h->zsum_dev = nullptr; h->w8_dev = nullptr; h->lut = nullptr;
+    h->stride = 1; h->phased = false; h->zsum_dev = nullptr; h->w8_dev = nullptr; h->lut = lut;
+    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0;
+    if (kind == 0) {
+        h->wofs_npad = ((N + 15) / 16) * 16;
+        const size_t pack_n = (size_t)Cin * h->wofs_npad;
+        hipError_t e = hipMalloc((void **)&h->wofs_dev, pack_n * sizeof(uint32_t));
+        if (e != hipSuccess) {
+            delete h;
+            return fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "%s: hipMalloc: %s", who, hipGetErrorString(e));
+        }
+        adapt::pack_row_offsets_kernel<<<(unsigned)((pack_n + 255) / 256), 256, 0, (hipStream_t)stream>>>(
+            w_dev, h->wofs_dev, Cin, N, h->wofs_npad, Cin, 1, (int)adapt::MODE_GEMM, 1 << (lut->bits - 1), (1 << lut->bits) - 1, lut->rs * 2);
+    }
     for (int half = 0; half <= lut->storage; ++half) {
         hipError_t e = hipMalloc((void **)&h->dt_dev[half], q.dt_bytes);
         if (e != hipSuccess) {
-            for (int j = 0; j < 2; ++j)
-                if (h->dt_dev[j]) (void)hipFree(h->dt_dev[j]);
-            delete h;
-            return fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "%s: hipMalloc(%zu): %s", who, q.dt_bytes,
+            const size_t want = q.dt_bytes;
+            adapt_weights_destroy(h);
+            return fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "%s: hipMalloc(%zu): %s", who, want,
                         hipGetErrorString(e));
         }
     }
     rc = pack_lines(lut, w_dev, q, h->dt_dev, (hipStream_t)stream);
     if (rc != ADAPT_OK) {
-        for (int j = 0; j < 2; ++j)
-            if (h->dt_dev[j]) (void)hipFree(h->dt_dev[j]);
-        delete h;
+        adapt_weights_destroy(h);
         return rc;
     }
     *out = h;
@@ -811,10 +863,25 @@ int adapt_weights_pack_conv_transpose2d(adapt_weights **out, const adapt_lut *lu
     h->Cp = h->Cc = h->n_tiles = 0; h->dt_bytes = 0;
     h->dt_dev[0] = h->dt_dev[1] = nullptr;
     h->zsum_dev = nullptr; h->w8_dev = nullptr; h->lut = lut;
+    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0;
     h->phased = kh % stride == 0 && kw % stride == 0 && stride <= 8;
     const size_t wbytes = (size_t)Cout * Cin * kh * kw;
     hipError_t e = hipMalloc((void **)&h->w8_dev, wbytes);
     if (e == hipSuccess) e = hipMemcpyAsync(h->w8_dev, w_dev, wbytes, hipMemcpyDeviceToDevice, (hipStream_t)stream);
+    {   // row offsets for the whole-table kernel, both forms
+        const int taps = kh * kw, hoff = 1 << (lut->bits - 1), mask = (1 << lut->bits) - 1;
+        h->wofs_npad = ((Cout + 15) / 16) * 16;
+        h->wofs1_npad = ((Cout * taps + 15) / 16) * 16;
+        const size_t n0 = (size_t)taps * Cin * h->wofs_npad, n1 = (size_t)Cin * h->wofs1_npad;
+        if (e == hipSuccess) e = hipMalloc((void **)&h->wofs_dev, n0 * sizeof(uint32_t));
+        if (e == hipSuccess) e = hipMalloc((void **)&h->wofs1_dev, n1 * sizeof(uint32_t));
+        if (e == hipSuccess) {
+            adapt::pack_row_offsets_kernel<<<(unsigned)((n0 + 255) / 256), 256, 0, (hipStream_t)stream>>>(
+                w_dev, h->wofs_dev, taps * Cin, Cout, h->wofs_npad, Cin, taps, (int)adapt::MODE_CONVT, hoff, mask, lut->rs * 2);
+            adapt::pack_row_offsets_kernel<<<(unsigned)((n1 + 255) / 256), 256, 0, (hipStream_t)stream>>>(
+                w_dev, h->wofs1_dev, Cin, Cout * taps, h->wofs1_npad, Cin, 1, (int)adapt::MODE_CONVT, hoff, mask, lut->rs * 2);
+        }
+    }
     if (e == hipSuccess && h->phased) {
         const LinesShape q = convt_phase_shape(lut->bits, Cout, Cin, kh, kw, stride);
         const size_t all = q.dt_bytes * stride * stride;
@@ -845,6 +912,9 @@ int adapt_weights_destroy(adapt_weights *h) {
     if (!h) return ADAPT_OK;
     for (int j = 0; j < 2; ++j)
         if (h->dt_dev[j]) (void)hipFree(h->dt_dev[j]);
+    if (h->ws.ptr) (void)hipFree(h->ws.ptr);
+    if (h->wofs_dev) (void)hipFree(h->wofs_dev);
+    if (h->wofs1_dev) (void)hipFree(h->wofs1_dev);
     if (h->zsum_dev) (void)hipFree(h->zsum_dev);
     if (h->w8_dev) (void)hipFree(h->w8_dev);
     delete h;
@@ -868,10 +938,10 @@ int adapt_approx_conv_transpose2d_packed(const adapt_weights *h, const int8_t *x
         const long long xt_bytes = (long long)N * (H + 2LL * (q.kh - 1)) * (W + 2LL * (q.kw - 1)) * q.Cp;
         if (xt_bytes < 0x7fffff00LL)
             return lines_conv_transpose2d(h->bits, h->storage, q, h->dt_dev, h->zsum_dev, x_dev, acc_dev, N, H, W, h->kh, h->kw,
-                                          h->stride, pad, (hipStream_t)stream);
+                                          h->stride, pad, (hipStream_t)stream, &h->ws);
     }
     // geometries outside the phase form (a single input pixel, output sizes that are no multiple of the stride)
-    return convt_rows(h->lut, x_dev, h->w8_dev, acc_dev, N, h->Cin, H, W, h->N, h->kh, h->kw, h->stride, pad, (hipStream_t)stream);
+    return convt_rows(h->lut, x_dev, h->w8_dev, acc_dev, N, h->Cin, H, W, h->N, h->kh, h->kw, h->stride, pad, (hipStream_t)stream, h);
 }
 
 int adapt_approx_linear_packed(const adapt_weights *h, const int8_t *a_dev, int32_t *acc_dev, int M, void *stream) {
@@ -882,7 +952,14 @@ int adapt_approx_linear_packed(const adapt_weights *h, const int8_t *a_dev, int3
     if (!a_dev || !acc_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_linear_packed: NULL pointer");
     if ((long long)M * h->Cp >= 0x7fffff00LL || (long long)M * h->N > 0x7fffffffLL)
         return fail(ADAPT_ERR_UNSUPPORTED, "adapt_approx_linear_packed: tensor with more than 2^31-1 elements");
-    return lines_linear(h->bits, h->storage, shape_of(h), h->dt_dev, a_dev, acc_dev, M, (hipStream_t)stream);
+    if (M < LINES_MIN_ROWS) {       // too few rows to amortise streaming the derived tables: whole-table kernel
+        Geometry g{};
+        g.mode = adapt::MODE_GEMM; g.M = M; g.N = h->N; g.Cin = h->Cin; g.taps = 1; g.kw = 1;
+        g.H = 1; g.W = 1; g.Wo = 1; g.HoWo = 1; g.sh = g.sw = g.dh = g.dw = 1; g.ph = g.pw = 0;
+        g.kstride = 1; g.img_stride = h->Cin;
+        return run_rows(h->lut, a_dev, nullptr, acc_dev, g, (hipStream_t)stream, h->wofs_dev, h->wofs_npad);
+    }
+    return lines_linear(h->bits, h->storage, shape_of(h), h->dt_dev, a_dev, acc_dev, M, (hipStream_t)stream, &h->ws);
 }
 
 int adapt_approx_conv2d_packed(const adapt_weights *h, const int8_t *x_dev, int32_t *acc_dev, int N, int H, int W, int stride_h,
@@ -901,7 +978,7 @@ int adapt_approx_conv2d_packed(const adapt_weights *h, const int8_t *x_dev, int3
     if (xt_bytes >= 0x7fffff00LL || (long long)N * h->N * Ho * Wo > 0x7fffffffLL || (long long)N * Ho * Wo > 0x7fffffffLL)
         return fail(ADAPT_ERR_UNSUPPORTED, "adapt_approx_conv2d_packed: tensor with more than 2^31-1 elements");
     return lines_conv2d(h->bits, h->storage, shape_of(h), h->dt_dev, x_dev, acc_dev, N, H, W, (int)Ho, (int)Wo, stride_h, stride_w,
-                        pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream);
+                        pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream, &h->ws);
 }
 
 /* ------------------------------------------------------------------ fp32 operations between layers */
@@ -953,16 +1030,29 @@ static int unary(const float *x_dev, float *y_dev, size_t n, int op, void *strea
 int adapt_tanh_f32(const float *x_dev, float *y_dev, size_t n, void *stream) { return unary(x_dev, y_dev, n, 0, stream, "adapt_tanh_f32"); }
 int adapt_sigmoid_f32(const float *x_dev, float *y_dev, size_t n, void *stream) { return unary(x_dev, y_dev, n, 1, stream, "adapt_sigmoid_f32"); }
 
-int adapt_lstm_cell_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh,
-                        const float *bias_dev, float *c_dev, float *h_dev, int B, int Hs, void *stream) {
-    if (B < 0 || Hs < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lstm_cell_f32: negative dimension");
+static int lstm_cell(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh, const float *bias_dev, float *c_dev,
+                     float *h_dev, int8_t *qh_dev, float s_h, int bits, int B, int Hs, void *stream, const char *who) {
+    if (B < 0 || Hs < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: negative dimension", who);
     const size_t n = (size_t)B * Hs;
     if (!n) return ADAPT_OK;
-    if (!acc_ih_dev || !acc_hh_dev || !c_dev || !h_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lstm_cell_f32: NULL pointer");
+    if (!acc_ih_dev || !acc_hh_dev || !c_dev || !h_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
     adapt::lstm_cell_kernel<<<(unsigned)((n + adapt::EW_THREADS - 1) / adapt::EW_THREADS), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(
-        acc_ih_dev, acc_hh_dev, s_ih, s_hh, bias_dev, c_dev, h_dev, B, Hs);
+        acc_ih_dev, acc_hh_dev, s_ih, s_hh, bias_dev, c_dev, h_dev, B, Hs, qh_dev, s_h, (float)((1 << (bits - 1)) - 1));
     HIP_TRY(hipGetLastError());
     return ADAPT_OK;
+}
+
+int adapt_lstm_cell_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh,
+                        const float *bias_dev, float *c_dev, float *h_dev, int B, int Hs, void *stream) {
+    return lstm_cell(acc_ih_dev, acc_hh_dev, s_ih, s_hh, bias_dev, c_dev, h_dev, nullptr, 1.0f, 8, B, Hs, stream, "adapt_lstm_cell_f32");
+}
+
+int adapt_lstm_cell_q_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh, const float *bias_dev,
+                          float *c_dev, float *h_dev, int8_t *qh_dev, float s_h, int bits, int B, int Hs, void *stream) {
+    if (!qh_dev && (size_t)B * Hs) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lstm_cell_q_f32: NULL pointer");
+    if (bits < 2 || bits > 8) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lstm_cell_q_f32: bits=%d not in [2,8]", bits);
+    if (!(s_h > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lstm_cell_q_f32: scale must be > 0");
+    return lstm_cell(acc_ih_dev, acc_hh_dev, s_ih, s_hh, bias_dev, c_dev, h_dev, qh_dev, s_h, bits, B, Hs, stream, "adapt_lstm_cell_q_f32");
 }
 
 }  // extern "C"

@@ -195,7 +195,7 @@ __global__ __launch_bounds__(EW_THREADS) void lstm_cell_kernel(const int32_t *__
                                                                const int32_t *__restrict__ acc_hh, float s_ih,
                                                                float s_hh, const float *__restrict__ bias,
                                                                float *__restrict__ c, float *__restrict__ h, int B,
-                                                               int Hs) {
+                                                               int Hs, int8_t *__restrict__ qh, float s_h, float Qh) {
     const size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
     if (i >= (size_t)B * Hs) return;
     const int b = (int)(i / Hs), j = (int)(i % Hs);
@@ -217,7 +217,9 @@ __global__ __launch_bounds__(EW_THREADS) void lstm_cell_kernel(const int32_t *__
     const float igg = ig * gg;
     const float cn = fc + igg;
     c[i] = cn;
-    h[i] = og * tanh_spec(cn);
+    const float hn = og * tanh_spec(cn);
+    h[i] = hn;
+    if (qh) qh[i] = (int8_t)quant1(hn, s_h, Qh);      // the next step's operand, same quantiser as quantize_kernel
 }
 
 }  // namespace adapt

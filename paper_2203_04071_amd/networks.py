@@ -35,6 +35,35 @@ def quantize_weights(w, bits):
     return B.adapt_quantize_f32(w, s, bits), s
 
 
+class Captured:
+    """One forward pass of a calibrated network recorded into a HIP graph and replayed as a single launch.
+
+    The networks are launch-bound chains of small kernels; a graph removes the per-launch host cost.  Recording needs
+    a pass that neither allocates through the library nor reads anything back: scales must already be frozen and every
+    packed-weights handle must have run once at this input size (its workspace is then large enough).  The graph holds
+    the addresses of those workspaces: running one of the handles on a LARGER input afterwards re-allocates its
+    workspace and invalidates the graph."""
+
+    def __init__(self, net, x):
+        self.net = net
+        self.x = x.clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            net.forward(self.x)             # sizes every workspace, on the stream family the capture will use
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            self.out = net.forward(self.x)
+
+    def replay(self, x=None):
+        if x is not None:
+            self.x.copy_(x)
+        self.graph.replay()
+        return self.out
+
+
 class ResNet20:
     def __init__(self, cfg, device="cuda"):
         self.bits = cfg["bits"]
@@ -44,6 +73,7 @@ class ResNet20:
         # the weights are static: combine them with the table once (Sec. III-B / III-C)
         self.pws = [B.adapt_weights_pack_conv2d(self.lut, qw) for qw, _ in self.qws]
         self.qfw, self.s_fw = quantize_weights(torch.from_numpy(cfg["fc_w"]).to(device), self.bits)
+        self.p_fw = B.adapt_weights_pack_linear(self.lut, self.qfw)
         self.fc_b = torch.from_numpy(cfg["fc_b"]).to(device)
         self.scales = None
         self.macs = None
@@ -76,7 +106,7 @@ class ResNet20:
         s_p = calibrated_scale(pooled, self.bits) if self.scales is None else self.scales[len(self.plan)]
         used.append(s_p)
         qp = B.adapt_quantize_f32(pooled, s_p, self.bits)
-        acc = B.adapt_approx_linear(self.lut, qp, self.qfw)
+        acc = B.adapt_approx_linear_packed(self.p_fw, qp)
         logits = B.adapt_dequant_i32(acc, _f(s_p) * _f(self.s_fw), acc.shape[0], acc.shape[1], 1, self.fc_b)
         if self.scales is None:
             self.scales = used
@@ -90,6 +120,7 @@ class LSTM:
         self.q_wih, self.s_wih = quantize_weights(torch.from_numpy(cfg["w_ih"]).to(device), self.bits)
         self.q_whh, self.s_whh = quantize_weights(torch.from_numpy(cfg["w_hh"]).to(device), self.bits)
         self.p_wih = B.adapt_weights_pack_linear(self.lut, self.q_wih)      # one long product over all time steps
+        self.p_whh = B.adapt_weights_pack_linear(self.lut, self.q_whh)      # 64-row products: pre-packed table-row offsets
         self.bias = torch.from_numpy(cfg["bias"]).to(device)
         self.Hs = cfg["w_hh"].shape[1]
         self.s_x = None
@@ -110,11 +141,12 @@ class LSTM:
         acc_hh = torch.empty((Bn, 4 * self.Hs), dtype=torch.int32, device=x.device)
         s_ih = _f(self.s_x) * _f(self.s_wih)
         s_hh = _f(s_h) * _f(self.s_whh)
+        B.adapt_quantize_f32(h, s_h, bits, out=qh)
         for t in range(T):
-            B.adapt_quantize_f32(h, s_h, bits, out=qh)
-            B.adapt_approx_linear(self.lut, qh, self.q_whh, out=acc_hh)
+            B.adapt_approx_linear_packed(self.p_whh, qh, out=acc_hh)
             h = hs[t]
-            B.adapt_lstm_cell_f32(acc_ih[t], acc_hh, s_ih, s_hh, self.bias, c, h)
+            # the cell also writes the quantised h that the next step multiplies
+            B.adapt_lstm_cell_q_f32(acc_ih[t], acc_hh, s_ih, s_hh, self.bias, c, h, qh, s_h, bits)
         return dict(hs=hs, c=c, acc_ih=acc_ih, acc_hh_last=acc_hh, s_x=self.s_x, s_h=s_h)
 
 

@@ -132,6 +132,13 @@ def test_lstm_cell_bit_exact(B, Bn, Hs):
         hd = torch.empty((Bn, Hs), dtype=torch.float32, device="cuda")
         B.adapt_lstm_cell_f32(dev(a1), dev(a2), s1, s2, dev(b) if b is not None else None, cd, hd)
         assert bits_equal(host(hd), h_w) and bits_equal(host(cd), c_w)
+        # fused variant: same cell, plus the quantised h of the next step
+        cd = dev(c)
+        qd = torch.empty((Bn, Hs), dtype=torch.int8, device="cuda")
+        s_h = np.float32(1.0) / np.float32(63)
+        B.adapt_lstm_cell_q_f32(dev(a1), dev(a2), s1, s2, dev(b) if b is not None else None, cd, hd, qd, s_h, 7)
+        assert bits_equal(host(hd), h_w) and bits_equal(host(cd), c_w)
+        assert (host(qd) == orc.quantize(h_w, s_h, 7)).all()
 
 
 # ------------------------------------------------------------------ table-lookup linear layer
@@ -402,6 +409,37 @@ def test_linear_long_routes_through_lines_kernel_and_split_tables(B):
             assert (host(B.adapt_approx_linear_packed(pw, dev(A))) == want).all()
 
 
+# Long linear layers: every variant of the derived-table kernel (rows per lane 8 / 4 / 2 by how many workgroups the
+# shape gives on 256 compute units, regular or ragged row count, 8-bit or narrower index, signed or split table).
+LINES_LINEAR = [
+    (8192, 40, 256), (8197, 40, 256),        # 8 rows per lane
+    (4096, 33, 256), (4099, 64, 250),        # 4 rows per lane
+    (4096, 32, 16), (4101, 100, 9),          # 2 rows per lane
+]
+
+
+@pytest.mark.parametrize("kind", ["b8", "b8wide", "b6", "b5wide"])
+@pytest.mark.parametrize("shape", LINES_LINEAR)
+def test_linear_lines_kernel_variants(B, kind, shape):
+    M, K, N = shape
+    bits = {"b8": 8, "b8wide": 8, "b6": 6, "b5wide": 5}[kind]
+    rng = np.random.default_rng(M + K + N + bits)
+    if kind.endswith("wide"):
+        n = 1 << bits
+        lut = rng.integers(-2**31, 2**31 - 1, size=(n, n), dtype=np.int64).astype(np.int32)
+    else:
+        lut = wl.make_lut(bits)
+    L = B.Lut(lut, bits)
+    A = wl.random_i8(rng, (M, K), bits, "gauss")
+    W = wl.random_i8(rng, (N, K), bits)
+    want = orc.approx_linear(lut, bits, A, W, threads=8)
+    pw = B.adapt_weights_pack_linear(L, dev(W))
+    got = host(B.adapt_approx_linear_packed(pw, dev(A)))
+    assert (got == want).all()
+    # short products with the same handle take the whole-table kernel with pre-packed offsets
+    assert (host(B.adapt_approx_linear_packed(pw, dev(A[:37]))) == want[:37]).all()
+
+
 PACKED_CONV = [
     # N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw
     (1, 8, 4, 4, 8, 3, 3, 1, 1, 1, 1, 1, 1),
@@ -518,3 +556,30 @@ def test_conv_transpose2d_packed_rect_kernel_and_wide_table(B):
     cnt[0, :] = cnt[-1, :] = cnt[:, 0] = cnt[:, -1] = 2
     cnt[0, 0] = cnt[0, -1] = cnt[-1, 0] = cnt[-1, -1] = 1
     assert (got == (3 * 4 * cnt)[None, None]).all()
+
+
+# ------------------------------------------------------------------ HIP-graph replay of a network
+
+def test_graph_replay_matches_eager(B):
+    """A recorded forward pass gives, on every replay (with eager work and synchronisations in between), exactly what
+    the eager pass gives; checked on reduced sizes of the CNN, LSTM and generator configurations."""
+    from paper_2203_04071_amd import networks as gnet
+    c4 = wl.config4(seq=6, batch=8)
+    c5 = wl.config5(bits=6, batch=8)
+    c3 = wl.config3(batch=8)
+    cases = [(gnet.ResNet20(c3), dev(c3["x"]), "logits"), (gnet.LSTM(c4), dev(c4["x"]), "hs"), (gnet.DCGAN(c5), dev(c5["z"]), "out")]
+    for net, x, key in cases:
+        want = host(net.forward(x)[key])            # calibrates
+        assert bits_equal(host(net.forward(x)[key]), want)
+        cap = gnet.Captured(net, x)
+        for rep in range(3):
+            got = cap.replay()[key]
+            torch.cuda.synchronize()
+            assert bits_equal(host(got), want), (type(net).__name__, rep)
+            # eager work between replays, on other data
+            other = host(net.forward(x * 0.5)[key])
+            assert other.shape == want.shape
+        # a different input through the same graph
+        x2 = x * 0.75
+        want2 = host(net.forward(x2)[key])
+        assert bits_equal(host(cap.replay(x2)[key]), want2)
