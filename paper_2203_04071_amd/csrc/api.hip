@@ -441,8 +441,8 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     p.m_tiles = (c.M + 128 * R - 1) / (128 * R);
     // one base offset per lane is enough when the R rows of a lane are equally spaced in xt
     const bool regular = (c.M % R == 0) && (c.HoWo == 1 || c.Wo % R == 0);
-    const bool xmajor = c.xmajor && R == 8 && regular;
-    if (c.xmajor && !xmajor) return fail(ADAPT_ERR_HIP, "lines path: x-major copy without 8 regular rows per lane");
+    const bool xmajor = c.xmajor && R == 8 && c.M % 8 == 0 && c.Wo % 4 == 0;
+    if (c.xmajor && !xmajor) return fail(ADAPT_ERR_HIP, "lines path: x-major copy without 8 rows per lane in runs of 4 pixels");
     int rc = ADAPT_OK;
     for (int first = 0; first < n_phases && rc == ADAPT_OK; first += 4) {       // up to four phases per launch
         p.phases = n_phases - first < 4 ? n_phases - first : 4;
@@ -471,21 +471,36 @@ int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     const int K = q.Cin, Kp = q.Cp;
     int8_t *tmp = nullptr;
     const int8_t *xt = a;
-    if (Kp != K) {
-        int wrc = ws_get(ws, (size_t)M * Kp + 16, s, (void **)&tmp);
-        if (wrc) return wrc;
-        const size_t total = (size_t)M * Kp;
-        size_t blocks = (total + 255) / 256;
-        if (blocks > 65536) blocks = 65536;
-        adapt::pad_rows_kernel<<<(unsigned)blocks, 256, 0, s>>>(a, tmp, M, K, Kp);
-        xt = tmp;
-    }
     LinesCall c;
-    c.M = M; c.HoWo = 1; c.Wo = 1; c.img_stride = Kp;
-    c.oy_stride = c.ox_stride = c.ky_stride = c.kx_stride = 0;
-    c.xmajor = 0; c.ch_stride = 0;
-    c.out_plane = 1; c.out_sy = 0; c.out_sx = 0;
+    c.M = M;
     c.phases.resize(1);
+    if (lines_rows_per_lane(M, q.n_tiles) == 8 && M % 8 == 0) {
+        // x-major copy: one image of one row of M pixels with K channels; a lane's 8 rows x 4 inner indices are 32
+        // contiguous bytes instead of 8 words that are a whole matrix row apart
+        int wrc = ws_get(ws, (size_t)M * Kp + 64, s, (void **)&tmp);
+        if (wrc) return wrc;
+        dim3 grid((unsigned)((M + 63) / 64), (unsigned)((Kp / 4 + 15) / 16));
+        adapt::rows_to_xmajor_kernel<<<grid, 256, 0, s>>>(a, tmp, M, K, Kp);
+        xt = tmp;
+        c.HoWo = M; c.Wo = M; c.img_stride = 0;
+        c.oy_stride = c.ky_stride = 0; c.ox_stride = c.kx_stride = 4;
+        c.xmajor = 1; c.ch_stride = M;
+        c.out_plane = 1; c.out_sy = 0; c.out_sx = q.N;
+    } else {
+        if (Kp != K) {
+            int wrc = ws_get(ws, (size_t)M * Kp + 16, s, (void **)&tmp);
+            if (wrc) return wrc;
+            const size_t total = (size_t)M * Kp;
+            size_t blocks = (total + 255) / 256;
+            if (blocks > 65536) blocks = 65536;
+            adapt::pad_rows_kernel<<<(unsigned)blocks, 256, 0, s>>>(a, tmp, M, K, Kp);
+            xt = tmp;
+        }
+        c.HoWo = 1; c.Wo = 1; c.img_stride = Kp;
+        c.oy_stride = c.ox_stride = c.ky_stride = c.kx_stride = 0;
+        c.xmajor = 0; c.ch_stride = 0;
+        c.out_plane = 1; c.out_sy = 0; c.out_sx = 0;
+    }
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s);
     return ws_put(ws, tmp, s, rc);
 }
@@ -498,7 +513,7 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     // With 8 rows per lane that are 8 consecutive output pixels of a stride-1 convolution, the copy is laid
     // out so that these rows' activations are contiguous (one wide load per lane instead of one per row).
     const int M = N * Ho * Wo;
-    const int xmajor = (lines_rows_per_lane(M, q.n_tiles) == 8 && Wo % 8 == 0 && sw == 1 && q.Cc % 4 == 0) ? 1 : 0;
+    const int xmajor = (lines_rows_per_lane(M, q.n_tiles) == 8 && Wo % 4 == 0 && M % 8 == 0 && sw == 1 && q.Cc % 4 == 0) ? 1 : 0;
     int8_t *xt = nullptr;
     {
         int wrc = ws_get(ws, xt_bytes + 64, s, (void **)&xt);
@@ -539,7 +554,7 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
     const int Qy = Ho / st, Qx = Wo / st;
     const int M = N * Qy * Qx;
     const size_t xt_bytes = (size_t)N * Hp * Wp * Cp;
-    const int xmajor = (lines_rows_per_lane(M, q.n_tiles * st * st) == 8 && Qx % 8 == 0 && q.Cc % 4 == 0) ? 1 : 0;
+    const int xmajor = (lines_rows_per_lane(M, q.n_tiles * st * st) == 8 && Qx % 4 == 0 && M % 8 == 0 && q.Cc % 4 == 0) ? 1 : 0;
     int8_t *xt = nullptr;
     {
         int wrc = ws_get(ws, xt_bytes + 64, s, (void **)&xt);

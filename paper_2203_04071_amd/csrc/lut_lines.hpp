@@ -70,7 +70,7 @@ __device__ __forceinline__ T pick4(const T *v, int i) {
 // NCHW int8 -> zero-padded copy, Cp (a multiple of 8) channels per pixel, in one of two orders:
 //   xmajor == 0: channel-last            [N][H + 2 ph][W + 2 pw][Cp]
 //   xmajor == 1: groups of four channels [N][H + 2 ph][Cp / 4][W + 2 pw][4]  (the four channel bytes of
-//                consecutive pixels are adjacent, so a lane's 8 rows x 4 channels are 32 contiguous bytes)
+//                consecutive pixels are adjacent, so 4 rows x 4 channels of a lane are 16 contiguous bytes)
 __global__ void pad_channels_last_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ xt, int N, int C, int H,
                                          int W, int ph, int pw, int Cp, int xmajor) {
     const int Hp = H + 2 * ph, Wp = W + 2 * pw;
@@ -106,6 +106,40 @@ __global__ void pad_rows_kernel(const int8_t *__restrict__ a, int8_t *__restrict
         const int k = (int)(i % Kp);
         const size_t m = i / Kp;
         at[i] = k < K ? a[m * K + k] : (int8_t)0;
+    }
+}
+
+// [M][K] int8 -> [Kp / 4][M][4]: for four consecutive inner indices the bytes of consecutive rows are adjacent (the
+// x-major order above with one image of one row), zero fill beyond K.  One workgroup of 256 threads moves a tile of
+// 64 rows x 64 inner indices through LDS so that both the reads (along K) and the writes (along M) coalesce.
+__global__ __launch_bounds__(256) void rows_to_xmajor_kernel(const int8_t *__restrict__ a, int8_t *__restrict__ at, int M, int K,
+                                                            int Kp) {
+    __shared__ uint32_t tile[16][65];
+    const int m0 = blockIdx.x * 64, c0 = blockIdx.y * 16;      // c counts groups of four inner indices
+    const int tid = threadIdx.x;
+    const bool fast = (K % 4 == 0) && ((reinterpret_cast<uintptr_t>(a) & 3u) == 0);
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+        const int ml = pass * 16 + tid / 16, c = tid % 16;
+        const int m = m0 + ml, k = (c0 + c) * 4;
+        uint32_t v = 0;
+        if (m < M) {
+            if (fast) {
+                if (k < K) v = *reinterpret_cast<const uint32_t *>(a + (size_t)m * K + k);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (k + q < K) v |= (uint32_t)(uint8_t)a[(size_t)m * K + k + q] << (8 * q);
+            }
+        }
+        tile[c][ml] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+        const int c = pass * 4 + tid / 64, ml = tid % 64;
+        const int m = m0 + ml;
+        if (m < M && (c0 + c) * 4 < Kp) *reinterpret_cast<uint32_t *>(at + ((size_t)(c0 + c) * M + m) * 4) = tile[c][ml];
     }
 }
 
@@ -572,7 +606,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     constexpr int WAIT_D = 0x0F70 | D;
     constexpr int WAIT_ALL = 0x0F70;
     static_assert(D + A < 16, "vmcnt immediate");
-    static_assert(!XMAJOR || (REGULAR && R == 8), "x-major activations: 8 regular rows per lane");
+    static_assert(!XMAJOR || (REGULAR && R == 8), "x-major activations: 8 rows per lane in two runs of 4 pixels");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -609,14 +643,16 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
         }
     };
 
-    uint32_t base[REGULAR ? 1 : R];
+    // XMAJOR: the 8 rows of a lane are two runs of 4 consecutive output pixels (each inside one image row), one base each
+    constexpr int NB = XMAJOR ? 2 : (REGULAR ? 1 : R);
+    uint32_t base[NB];
     uint32_t row_step = 0;
     {
         int r0 = mt * (128 * R) + rs * R;
         if (REGULAR && r0 > p.M - R) r0 = p.M - R;
 #pragma unroll
-        for (int i = 0; i < (REGULAR ? 1 : R); ++i) {
-            int r = r0 + i;
+        for (int i = 0; i < NB; ++i) {
+            int r = r0 + (XMAJOR ? 4 * i : i);
             if (r >= p.M) r = p.M - 1;
             const int img = r / p.HoWo, pix = r - img * p.HoWo;
             const int oy = pix / p.Wo, ox = pix - oy * p.Wo;
@@ -628,10 +664,10 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     // activations of a group of four steps: element i of the register block = row i, one byte per step
     constexpr int AQ = (R + 3) / 4;
     auto load_acts = [&](u32x4_t *a, const int8_t *xrow) {
-        if (XMAJOR) {       // rows are consecutive pixels: 8 rows x 4 channel bytes are 32 contiguous bytes
-            asm volatile("global_load_dwordx4 %0, %2, %3\n\tglobal_load_dwordx4 %1, %2, %3 offset:16"
+        if (XMAJOR) {       // 4 consecutive pixels x 4 channel bytes are 16 contiguous bytes
+            asm volatile("global_load_dwordx4 %0, %2, %4\n\tglobal_load_dwordx4 %1, %3, %4"
                          : "=&v"(a[0]), "=&v"(a[AQ - 1])
-                         : "v"(base[0]), "s"(xrow));
+                         : "v"(base[0]), "v"(base[NB - 1]), "s"(xrow));
             return;
         }
 #pragma unroll
@@ -758,7 +794,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
         int img0 = 0, pix0 = 0;
         if (REGULAR) { img0 = r0 / p.HoWo; pix0 = r0 - img0 * p.HoWo; }
         if constexpr (XMAJOR) {
-            // 8 consecutive pixels of one output row and one channel
+            // two runs of 4 consecutive pixels of one channel
             uint32_t v[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -766,18 +802,22 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
 #pragma unroll
                 for (int c = 1; c < 8; ++c) v[i] = (j == c) ? acc[i * 8 + c] : v[i];
             }
-            const int a0 = pix0 / p.Wo, b0 = pix0 - a0 * p.Wo;
-            int32_t *q0 = p.out + ((size_t)img0 * p.N + n) * p.out_plane + out_off + a0 * p.out_sy + b0 * p.out_sx;
-            if (r0 + 8 <= p.M) {
-                if (p.shift < 0 && p.out_sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {       // two 16-byte stores
-                    reinterpret_cast<uint4 *>(q0)[0] = make_uint4(v[0], v[1], v[2], v[3]);
-                    reinterpret_cast<uint4 *>(q0)[1] = make_uint4(v[4], v[5], v[6], v[7]);
-                } else {
-                    const int sx = p.out_sx;
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        if (p.shift < 0) q0[i * sx] = (int32_t)v[i];
-                        else q0[i * sx] = (int32_t)((uint32_t)q0[i * sx] + (v[i] << p.shift));
+            for (int hq = 0; hq < 2; ++hq) {
+                const int r = r0 + 4 * hq;
+                if (r + 4 <= p.M) {
+                    const int img = r / p.HoWo, pix = r - img * p.HoWo;
+                    const int a0 = pix / p.Wo, b0 = pix - a0 * p.Wo;
+                    int32_t *q0 = p.out + ((size_t)img * p.N + n) * p.out_plane + out_off + a0 * p.out_sy + b0 * p.out_sx;
+                    if (p.shift < 0 && p.out_sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
+                        *reinterpret_cast<uint4 *>(q0) = make_uint4(v[4 * hq], v[4 * hq + 1], v[4 * hq + 2], v[4 * hq + 3]);
+                    } else {
+                        const int sx = p.out_sx;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            if (p.shift < 0) q0[i * sx] = (int32_t)v[4 * hq + i];
+                            else q0[i * sx] = (int32_t)((uint32_t)q0[i * sx] + (v[4 * hq + i] << p.shift));
+                        }
                     }
                 }
             }
