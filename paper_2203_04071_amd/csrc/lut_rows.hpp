@@ -105,6 +105,39 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
 #pragma unroll
     for (int n = 0; n < NT; ++n) acc[n] = 0;
 
+    // Linear layers whose rows are word-aligned: the activations of this lane's K slice are fetched as whole words, 32
+    // inner indices at a time and one block ahead of their use, so that the loop never waits for a byte load.
+    if (p.mode == MODE_GEMM && p.kstride == 1 && (p.Cin & 3) == 0 && (kc & 3) == 0 &&
+        (reinterpret_cast<uintptr_t>(p.x) & 3u) == 0) {
+        const uint32_t *xw = reinterpret_cast<const uint32_t *>(xb);       // row of this lane
+        auto fetch = [&](uint32_t *dst, int kk) {
+#pragma unroll
+            for (int d = 0; d < 8; ++d) dst[d] = (kk + 4 * d < k_end) ? xw[(kk >> 2) + d] : 0u;
+        };
+        uint32_t cur[8], nxt[8];
+        if (k < k_end) fetch(nxt, k);
+        while (k < k_end) {
+#pragma unroll
+            for (int d = 0; d < 8; ++d) cur[d] = nxt[d];
+            if (k + 32 < k_end) fetch(nxt, k + 32);
+            const int cnt = min(32, k_end - k);
+#pragma unroll
+            for (int d = 0; d < 8; ++d) {
+                if (4 * d < cnt) {          // uniform in the wave
+#pragma unroll
+                    for (int bq = 0; bq < 4; ++bq) {
+                        const int a = (int)(int8_t)(cur[d] >> (8 * bq));
+                        const uint32_t a2 = (uint32_t)(((a + p.hoff) & p.mask) << 1);
+                        const uint32_t *w1 = p.wofs + (size_t)(k + 4 * d + bq) * p.Npad + n0;
+#pragma unroll
+                        for (int n = 0; n < NT; ++n) acc[n] += lds_entry<SIGNED>(smem, w1[n] + a2);
+                    }
+                }
+            }
+            k += cnt;
+        }
+    }
+
     while (k < k_end) {
         const int t = k / p.Cin;
         const int c0 = k - t * p.Cin;
