@@ -76,13 +76,17 @@ def build_step(cfg_id, bits, torch, B, gnet, wl, eager=False):
         B.adapt_quantize_f32(x, s_x, 8, out=qx)
         pw = B.adapt_weights_pack_conv2d(L, qw)      # weights are static: packed once, outside the timed steps
 
+        # one fused call: the quantiser runs in the kernel that lays the input out for the product, the rescaling in
+        # the product kernel (two launches; --eager times the four separate calls instead)
         def core():
-            B.adapt_approx_conv2d_packed(pw, qx, (1, 1), (1, 1), out=acc)
+            B.adapt_conv2d_layer_f32(pw, x, s_x, s_out, (1, 1), (1, 1), out=y)
 
-        def step():
+        def step_separate():
             B.adapt_quantize_f32(x, s_x, 8, out=qx)
-            core()
+            B.adapt_approx_conv2d_packed(pw, qx, (1, 1), (1, 1), out=acc)
             B.adapt_dequant_i32(acc, s_out, 32, 64, 1024, out=y)
+
+        step = step_separate if eager else core
         return step, core, wl.lut_macs_conv2d(32, 64, 32, 32, 64, 3, 3, 1, 1, 1, 1), \
             "config2: approx_conv2d 3x3 s1 p1, batch 32, 64->64 ch, 32x32, 8-bit table", L
     if cfg_id == 3:

@@ -156,6 +156,27 @@ int adapt_approx_conv_transpose2d_packed(const adapt_weights *w, const int8_t *x
                                          int pad, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * Whole layers on packed weights with fp32 activations on both sides (Sec. III-A/III-B: a layer quantises its input,
+ * multiplies through the table and rescales the sums):
+ *     q = quantise(x, s_x, bits of the table)                 exactly as adapt_quantize_f32
+ *     acc = table product of q with the packed weights        exactly as the *_packed entry points
+ *     y = float(acc) * s_out, then + bias[c] if bias_dev      exactly as adapt_dequant_i32
+ *     act 0: nothing; 1: y = y > 0 ? y : 0 (adapt_relu_f32); 2: adapt_tanh_f32
+ * The quantiser runs inside the kernel that lays the activations out for the product, and (single-pass tables) the
+ * rescaling inside the product kernel, so a layer is two launches instead of four or five and the int8 / int32
+ * intermediates never reach memory.  y_dev has the shape of the int32 output of the corresponding *_packed call
+ * and also serves as scratch for the sums where they cannot be rescaled in the product kernel.  s_out = s_x * s_w,
+ * formed in fp32 by the caller; bias_dev [channels] or NULL.
+ * ---------------------------------------------------------------------------------------------- */
+int adapt_linear_layer_f32(const adapt_weights *w, const float *x_dev, float *y_dev, int M, float s_x, float s_out,
+                           const float *bias_dev, int act, void *stream);
+int adapt_conv2d_layer_f32(const adapt_weights *w, const float *x_dev, float *y_dev, int N, int H, int W, int stride_h,
+                           int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, float s_x, float s_out,
+                           const float *bias_dev, int act, void *stream);
+int adapt_conv_transpose2d_layer_f32(const adapt_weights *w, const float *x_dev, float *y_dev, int N, int H, int W, int pad,
+                                     float s_x, float s_out, const float *bias_dev, int act, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
  * fp32 operations between approximate layers.  Each element is produced by single IEEE fp32
  * operations in the stated order (no fused multiply-add unless stated), so that the integers the next
  * quantiser produces are reproducible.  In-place use (y_dev == x_dev) is allowed.

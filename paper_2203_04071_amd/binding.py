@@ -27,6 +27,7 @@ EXPORTS = [
     "adapt_weights_pack_linear", "adapt_weights_pack_conv2d", "adapt_weights_pack_conv_transpose2d",
     "adapt_weights_destroy",
     "adapt_approx_linear_packed", "adapt_approx_conv2d_packed", "adapt_approx_conv_transpose2d_packed",
+    "adapt_linear_layer_f32", "adapt_conv2d_layer_f32", "adapt_conv_transpose2d_layer_f32",
     "adapt_relu_f32", "adapt_add_f32", "adapt_avgpool_hw_f32", "adapt_shortcut_a_f32",
     "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32", "adapt_lstm_cell_q_f32",
 ]
@@ -69,6 +70,9 @@ def load() -> ctypes.CDLL:
     L.adapt_weights_pack_conv_transpose2d.argtypes = [ctypes.POINTER(vp), vp, vp, i32, i32, i32, i32, i32, vp]
     L.adapt_approx_conv_transpose2d_packed.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
     L.adapt_weights_destroy.argtypes = [vp]
+    L.adapt_linear_layer_f32.argtypes = [vp, vp, vp, i32, f32, f32, vp, i32, vp]
+    L.adapt_conv2d_layer_f32.argtypes = [vp, vp, vp] + [i32] * 9 + [f32, f32, vp, i32, vp]
+    L.adapt_conv_transpose2d_layer_f32.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, f32, vp, i32, vp]
     L.adapt_approx_linear_packed.argtypes = [vp, vp, vp, i32, vp]
     L.adapt_approx_conv2d_packed.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
     L.adapt_relu_f32.argtypes = [vp, vp, sz, vp]
@@ -365,3 +369,43 @@ def adapt_lstm_cell_q_f32(acc_ih, acc_hh, s_ih: float, s_hh: float, bias, c, h, 
                                       _ptr(bias, torch.float32), _ptr(c, torch.float32), _ptr(h, torch.float32),
                                       _ptr(qh, torch.int8), float(s_h), bits, B, Hs, _stream(stream)))
     return h, c, qh
+
+
+ACT_NONE, ACT_RELU, ACT_TANH = 0, 1, 2
+
+
+def adapt_linear_layer_f32(pw: PackedWeights, x, s_x, s_out, bias=None, act=ACT_NONE, out=None, stream=None):
+    M, K = x.shape
+    N, K2 = pw.shape
+    assert K == K2 and pw.kind == "linear"
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=x.device)
+    _chk(load().adapt_linear_layer_f32(pw.handle, _ptr(x, torch.float32), _ptr(out, torch.float32), M, float(s_x), float(s_out),
+                                       _ptr(bias, torch.float32), act, _stream(stream)))
+    return out
+
+
+def adapt_conv2d_layer_f32(pw: PackedWeights, x, s_x, s_out, stride=(1, 1), pad=(0, 0), dil=(1, 1), bias=None, act=ACT_NONE,
+                           out=None, stream=None):
+    N, Cin, H, W = x.shape
+    Cout, Cin2, kh, kw = pw.shape
+    assert Cin == Cin2 and pw.kind == "conv2d"
+    if out is None:
+        Ho, Wo = conv_out_hw(H, W, kh, kw, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1])
+        out = torch.empty((N, Cout, Ho, Wo), dtype=torch.float32, device=x.device)
+    _chk(load().adapt_conv2d_layer_f32(pw.handle, _ptr(x, torch.float32), _ptr(out, torch.float32), N, H, W, stride[0], stride[1],
+                                       pad[0], pad[1], dil[0], dil[1], float(s_x), float(s_out), _ptr(bias, torch.float32), act,
+                                       _stream(stream)))
+    return out
+
+
+def adapt_conv_transpose2d_layer_f32(pw: PackedWeights, x, s_x, s_out, pad=0, bias=None, act=ACT_NONE, out=None, stream=None):
+    N, Cin, H, W = x.shape
+    Cin2, Cout, kh, kw = pw.shape
+    assert Cin == Cin2 and pw.kind == "conv_transpose2d"
+    if out is None:
+        Ho, Wo = (H - 1) * pw.stride - 2 * pad + kh, (W - 1) * pw.stride - 2 * pad + kw
+        out = torch.empty((N, Cout, Ho, Wo), dtype=torch.float32, device=x.device)
+    _chk(load().adapt_conv_transpose2d_layer_f32(pw.handle, _ptr(x, torch.float32), _ptr(out, torch.float32), N, H, W, pad,
+                                                 float(s_x), float(s_out), _ptr(bias, torch.float32), act, _stream(stream)))
+    return out

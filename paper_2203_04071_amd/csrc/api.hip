@@ -73,6 +73,24 @@ int ws_put(Workspace *cache, void *p, hipStream_t s, int rc) {
     return rc;
 }
 
+// Optional fp32 ends of a layer call.
+struct LayerIO {
+    const float *xf = nullptr;      // fp32 activations, quantised while the activation copy is made (the int8 pointer is unused)
+    float s_x = 1.0f, Q = 127.0f;
+    int deq = 0;                    // the output buffer receives fp32 y = float(acc) * s_out (+ bias[c]) (act 1: ReLU, 2: tanh)
+    int act = 0;
+    float s_out = 1.0f;
+    const float *bias = nullptr;
+    // rescaling inside the product kernel needs a single table pass and an activation it knows
+    bool fused(int storage) const { return deq && storage == 0 && act <= 1; }
+};
+
+int finish_inplace(int32_t *buf, size_t n, size_t channels, size_t inner, const LayerIO &io, hipStream_t s) {
+    adapt::finish_inplace_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, s>>>(buf, n, channels, inner, io.s_out, io.bias, io.act);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
 }  // namespace
 
 struct adapt_lut {
@@ -269,7 +287,7 @@ struct Geometry {
 // prepacked: row offsets [K][prepacked_npad] made earlier by pack_row_offsets_kernel (prepacked_npad a multiple of 16),
 // or nullptr to pack `w` into a stream-ordered temporary.
 int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *out, const Geometry &g, hipStream_t s,
-             const uint32_t *prepacked = nullptr, int prepacked_npad = 0) {
+             const uint32_t *prepacked = nullptr, int prepacked_npad = 0, const LayerIO *io = nullptr) {
     const int bits = lut->bits;
     const long long Ktot = (long long)g.taps * g.Cin;
     if (g.M == 0 || g.N == 0) return ADAPT_OK;
@@ -314,6 +332,8 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     p.hoff = 1 << (bits - 1); p.mask = (1 << bits) - 1;
     p.a_zero2 = (1 << (bits - 1)) * 2; p.a_skip2 = (1 << bits) * 2;
     p.MT = MT; p.KS = KS;
+    const bool fuse = io && io->fused(lut->storage);
+    p.deq = fuse ? 1 : 0; p.act = fuse ? io->act : 0; p.scale = fuse ? io->s_out : 1.0f; p.bias = fuse ? io->bias : nullptr;
     dim3 grid((unsigned)((g.M + MT - 1) / MT), (unsigned)(Npad / NT));
     size_t lds = (size_t)lut->img_bytes;
     if (KS > 1 && (size_t)adapt::ROWS_THREADS * NT * 4 > lds) lds = (size_t)adapt::ROWS_THREADS * NT * 4;
@@ -327,6 +347,10 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     if (wofs) {
         hipError_t fe = hipFreeAsync(wofs, s);
         if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
+    }
+    if (rc == ADAPT_OK && io && io->deq && !fuse) {
+        const size_t inner = g.mode == adapt::MODE_GEMM ? 1 : (size_t)g.HoWo;
+        rc = finish_inplace(out, (size_t)g.M * g.N, (size_t)g.N, inner, *io, s);
     }
     return rc;
 }
@@ -427,7 +451,7 @@ int lines_rows_per_lane(int M, int n_tiles) {
 }
 
 int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *xt, const LinesCall &c,
-              int32_t *out, hipStream_t s) {
+              int32_t *out, hipStream_t s, const LayerIO *io = nullptr, bool may_fuse = true) {
     const int n_phases = (int)c.phases.size();
     const int R = lines_rows_per_lane(c.M, q.n_tiles * n_phases);
     adapt::LinesParams p;
@@ -439,6 +463,8 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     p.ch_stride = c.ch_stride;
     p.out_plane = c.out_plane; p.out_sy = c.out_sy; p.out_sx = c.out_sx;
     p.m_tiles = (c.M + 128 * R - 1) / (128 * R);
+    const bool fuse = may_fuse && io && io->fused(storage);
+    p.deq = fuse ? 1 : 0; p.act = fuse ? io->act : 0; p.scale = fuse ? io->s_out : 1.0f; p.bias = fuse ? io->bias : nullptr;
     // one base offset per lane is enough when the R rows of a lane are equally spaced in xt
     const bool regular = (c.M % R == 0) && (c.HoWo == 1 || c.Wo % R == 0);
     const bool xmajor = c.xmajor && R == 8 && c.M % 8 == 0 && c.Wo % 4 == 0;
@@ -467,7 +493,10 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
 
 // activation side of a linear layer: A itself when its rows are a multiple of 32 bytes, else a zero-padded copy
 int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *a, int32_t *out, int M, hipStream_t s,
-                 Workspace *ws) {
+                 Workspace *ws, const LayerIO *io = nullptr) {
+    const adapt::SrcI8 src8{a};
+    const adapt::SrcF32 srcf{io ? io->xf : nullptr, io ? io->s_x : 1.0f, io ? io->Q : 1.0f};
+    const bool from_f32 = io && io->xf;
     const int K = q.Cin, Kp = q.Cp;
     int8_t *tmp = nullptr;
     const int8_t *xt = a;
@@ -480,20 +509,22 @@ int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
         int wrc = ws_get(ws, (size_t)M * Kp + 64, s, (void **)&tmp);
         if (wrc) return wrc;
         dim3 grid((unsigned)((M + 63) / 64), (unsigned)((Kp / 4 + 15) / 16));
-        adapt::rows_to_xmajor_kernel<<<grid, 256, 0, s>>>(a, tmp, M, K, Kp);
+        if (from_f32) adapt::rows_to_xmajor_kernel<<<grid, 256, 0, s>>>(srcf, tmp, M, K, Kp);
+        else adapt::rows_to_xmajor_kernel<<<grid, 256, 0, s>>>(src8, tmp, M, K, Kp);
         xt = tmp;
         c.HoWo = M; c.Wo = M; c.img_stride = 0;
         c.oy_stride = c.ky_stride = 0; c.ox_stride = c.kx_stride = 4;
         c.xmajor = 1; c.ch_stride = M;
         c.out_plane = 1; c.out_sy = 0; c.out_sx = q.N;
     } else {
-        if (Kp != K) {
+        if (Kp != K || from_f32) {
             int wrc = ws_get(ws, (size_t)M * Kp + 16, s, (void **)&tmp);
             if (wrc) return wrc;
             const size_t total = (size_t)M * Kp;
             size_t blocks = (total + 255) / 256;
             if (blocks > 65536) blocks = 65536;
-            adapt::pad_rows_kernel<<<(unsigned)blocks, 256, 0, s>>>(a, tmp, M, K, Kp);
+            if (from_f32) adapt::pad_rows_kernel<<<(unsigned)blocks, 256, 0, s>>>(srcf, tmp, M, K, Kp);
+            else adapt::pad_rows_kernel<<<(unsigned)blocks, 256, 0, s>>>(src8, tmp, M, K, Kp);
             xt = tmp;
         }
         c.HoWo = 1; c.Wo = 1; c.img_stride = Kp;
@@ -501,13 +532,16 @@ int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
         c.xmajor = 0; c.ch_stride = 0;
         c.out_plane = 1; c.out_sy = 0; c.out_sx = 0;
     }
-    int rc = run_lines(bits, storage, q, dt, xt, c, out, s);
-    return ws_put(ws, tmp, s, rc);
+    int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io);
+    rc = ws_put(ws, tmp, s, rc);
+    if (rc == ADAPT_OK && io && io->deq && !io->fused(storage)) rc = finish_inplace(out, (size_t)M * q.N, (size_t)q.N, 1, *io, s);
+    return rc;
 }
 
 // activation side of a convolution: zero-padded channel-last copy of x
 int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *x, int32_t *out, int N, int H,
-                 int W, int Ho, int Wo, int sh, int sw, int ph, int pw, int dh, int dw, hipStream_t s, Workspace *ws) {
+                 int W, int Ho, int Wo, int sh, int sw, int ph, int pw, int dh, int dw, hipStream_t s, Workspace *ws,
+                 const LayerIO *io = nullptr) {
     const int Hp = H + 2 * ph, Wp = W + 2 * pw, Cp = q.Cp;
     const size_t xt_bytes = (size_t)N * Hp * Wp * Cp;
     // With 8 rows per lane that are 8 consecutive output pixels of a stride-1 convolution, the copy is laid
@@ -521,7 +555,10 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
         const size_t total = xt_bytes / 4;
         size_t blocks = (total + 255) / 256;
         if (blocks > 65536) blocks = 65536;
-        adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(x, xt, N, q.Cin, H, W, ph, pw, Cp, xmajor);
+        if (io && io->xf)
+            adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcF32{io->xf, io->s_x, io->Q}, xt, N, q.Cin, H, W, ph,
+                                                                             pw, Cp, xmajor);
+        else adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcI8{x}, xt, N, q.Cin, H, W, ph, pw, Cp, xmajor);
     }
     LinesCall c;
     c.M = M; c.HoWo = Ho * Wo; c.Wo = Wo;
@@ -532,8 +569,11 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     c.xmajor = xmajor; c.ch_stride = Wp;
     c.out_plane = Ho * Wo; c.out_sy = Wo; c.out_sx = 1;
     c.phases.resize(1);
-    int rc = run_lines(bits, storage, q, dt, xt, c, out, s);
-    return ws_put(ws, xt, s, rc);
+    int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io);
+    rc = ws_put(ws, xt, s, rc);
+    if (rc == ADAPT_OK && io && io->deq && !io->fused(storage))
+        rc = finish_inplace(out, (size_t)M * q.N, (size_t)q.N, (size_t)Ho * Wo, *io, s);
+    return rc;
 }
 
 // Transposed convolution as stride * stride stride-1 convolutions (see pack_line_tables_convt_kernel).  Needs kernel
@@ -547,7 +587,8 @@ LinesShape convt_phase_shape(int bits, int Cout, int Cin, int kh, int kw, int st
 }
 
 int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int32_t *zsum, const int8_t *x,
-                           int32_t *out, int N, int H, int W, int kh, int kw, int st, int pad, hipStream_t s, Workspace *ws) {
+                           int32_t *out, int N, int H, int W, int kh, int kw, int st, int pad, hipStream_t s, Workspace *ws,
+                           const LayerIO *io = nullptr) {
     const int Ty = q.kh, Tx = q.kw, Cp = q.Cp;
     const int Hp = H + 2 * (Ty - 1), Wp = W + 2 * (Tx - 1);
     const int Ho = (H - 1) * st - 2 * pad + kh, Wo = (W - 1) * st - 2 * pad + kw;
@@ -562,7 +603,10 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
         const size_t total = xt_bytes / 4;
         size_t blocks = (total + 255) / 256;
         if (blocks > 65536) blocks = 65536;
-        adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(x, xt, N, q.Cin, H, W, Ty - 1, Tx - 1, Cp, xmajor);
+        if (io && io->xf)
+            adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcF32{io->xf, io->s_x, io->Q}, xt, N, q.Cin, H, W,
+                                                                             Ty - 1, Tx - 1, Cp, xmajor);
+        else adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcI8{x}, xt, N, q.Cin, H, W, Ty - 1, Tx - 1, Cp, xmajor);
     }
     LinesCall c;
     c.M = M; c.HoWo = Qy * Qx; c.Wo = Qx;
@@ -583,11 +627,12 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
             f.dt_off = (long long)(ry * st + rx) * phase_u4;
             c.phases.push_back(f);
         }
-    int rc = run_lines(bits, storage, q, dt, xt, c, out, s);
-    rc = ws_put(ws, xt, s, rc);
-    if (rc != ADAPT_OK) return rc;
     // window taps over the zero border were looked up; the layer is defined over real pairs only
     const int Ly = kh - st - pad > 0 ? kh - st - pad : 0, Lx = kw - st - pad > 0 ? kw - st - pad : 0;
+    const bool border = Ly > 0 || Lx > 0;       // then the sums are corrected before they can be rescaled
+    int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io, !border);
+    rc = ws_put(ws, xt, s, rc);
+    if (rc != ADAPT_OK) return rc;
     const int nrows = 2 * Ly < Ho ? 2 * Ly : Ho, ncols = 2 * Lx < Wo ? 2 * Lx : Wo;
     const size_t planes = (size_t)N * q.N;
     const size_t work[2] = {planes * nrows * Wo, planes * (size_t)(Ho - nrows) * ncols};
@@ -599,6 +644,7 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
                                                                        Lx, region);
         HIP_TRY(hipGetLastError());
     }
+    if (io && io->deq && (border || !io->fused(storage))) return finish_inplace(out, planes * Ho * Wo, (size_t)q.N, (size_t)Ho * Wo, *io, s);
     return ADAPT_OK;
 }
 
@@ -658,7 +704,7 @@ int check_lut(const adapt_lut *lut, const char *who) {
 
 // transposed convolution on the rows kernel
 int convt_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *acc, int N, int Cin, int H, int W, int Cout, int kh,
-               int kw, int stride, int pad, hipStream_t s, const adapt_weights *h = nullptr) {
+               int kw, int stride, int pad, hipStream_t s, const adapt_weights *h = nullptr, const LayerIO *io = nullptr) {
     const int Ho = (H - 1) * stride - 2 * pad + kh, Wo = (W - 1) * stride - 2 * pad + kw;
     Geometry g{};
     if (H == 1 && W == 1 && pad == 0) {
@@ -667,13 +713,19 @@ int convt_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *
         g.mode = adapt::MODE_GEMM; g.M = N; g.N = Cout * kh * kw; g.Cin = Cin; g.taps = 1; g.kw = 1;
         g.H = 1; g.W = 1; g.Wo = 1; g.HoWo = 1; g.sh = g.sw = g.dh = g.dw = 1; g.ph = g.pw = 0;
         g.kstride = 1; g.img_stride = Cin; g.wt = 1;
+        if (io && io->deq) {
+            // here the output is [N][Cout][kh][kw] while the product's channel axis is Cout kh kw: rescale afterwards
+            int rc = h ? run_rows(lut, x, w, acc, g, s, h->wofs1_dev, h->wofs1_npad) : run_rows(lut, x, w, acc, g, s);
+            if (rc) return rc;
+            return finish_inplace(acc, (size_t)N * Cout * kh * kw, (size_t)Cout, (size_t)kh * kw, *io, s);
+        }
         return h ? run_rows(lut, x, w, acc, g, s, h->wofs1_dev, h->wofs1_npad) : run_rows(lut, x, w, acc, g, s);
     }
     g.mode = adapt::MODE_CONVT; g.M = N * Ho * Wo; g.N = Cout; g.Cin = Cin; g.taps = kh * kw; g.kw = kw;
     g.H = H; g.W = W; g.Wo = Wo; g.HoWo = Ho * Wo;
     g.sh = stride; g.sw = stride; g.ph = pad; g.pw = pad; g.dh = g.dw = 1;
     g.kstride = H * W; g.img_stride = Cin * H * W;
-    return h ? run_rows(lut, x, w, acc, g, s, h->wofs_dev, h->wofs_npad) : run_rows(lut, x, w, acc, g, s);
+    return h ? run_rows(lut, x, w, acc, g, s, h->wofs_dev, h->wofs_npad, io) : run_rows(lut, x, w, acc, g, s, nullptr, 0, io);
 }
 
 // transposed convolution with plain weights: the cheapest form the geometry allows
@@ -994,6 +1046,102 @@ int adapt_approx_conv2d_packed(const adapt_weights *h, const int8_t *x_dev, int3
         return fail(ADAPT_ERR_UNSUPPORTED, "adapt_approx_conv2d_packed: tensor with more than 2^31-1 elements");
     return lines_conv2d(h->bits, h->storage, shape_of(h), h->dt_dev, x_dev, acc_dev, N, H, W, (int)Ho, (int)Wo, stride_h, stride_w,
                         pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream, &h->ws);
+}
+
+/* ------------------------------------------------------------------ whole layers, fp32 in and out */
+
+static int layer_io(LayerIO *io, const adapt_weights *h, const float *x_dev, const float *y_dev, float s_x, float s_out,
+                    const float *bias_dev, int act, const char *who) {
+    if (!x_dev || !y_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
+    if (!(s_x > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: s_x must be > 0", who);
+    if (act < 0 || act > 2) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: act=%d not in {0, 1, 2}", who, act);
+    io->xf = x_dev; io->s_x = s_x; io->Q = (float)((1 << (h->bits - 1)) - 1);
+    io->deq = 1; io->act = act; io->s_out = s_out; io->bias = bias_dev;
+    return ADAPT_OK;
+}
+
+// int8 copy of fp32 activations in the handle's workspace, for the whole-table kernel
+static int quantize_into_ws(const adapt_weights *h, const LayerIO &io, size_t n, hipStream_t s, int8_t **q) {
+    int rc = ws_get(&h->ws, n + 64, s, (void **)q);
+    if (rc) return rc;
+    const int vec = (aligned16(io.xf) && aligned16(*q)) ? 1 : 0;
+    adapt::quantize_kernel<<<ew_grid(n / 16 + 1), adapt::EW_THREADS, 0, s>>>(io.xf, *q, n, io.s_x, io.Q, vec);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+int adapt_linear_layer_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int M, float s_x, float s_out,
+                           const float *bias_dev, int act, void *stream) {
+    const char *who = "adapt_linear_layer_f32";
+    int rc = check_weights(h, 0, who);
+    if (rc) return rc;
+    if (M < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: negative M", who);
+    if (M == 0) return ADAPT_OK;
+    LayerIO io;
+    if ((rc = layer_io(&io, h, x_dev, y_dev, s_x, s_out, bias_dev, act, who))) return rc;
+    if ((long long)M * h->Cp >= 0x7fffff00LL || (long long)M * h->N > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
+    hipStream_t s = (hipStream_t)stream;
+    int32_t *out = reinterpret_cast<int32_t *>(y_dev);
+    if (M < LINES_MIN_ROWS) {
+        int8_t *q = nullptr;
+        if ((rc = quantize_into_ws(h, io, (size_t)M * h->Cin, s, &q))) return rc;
+        Geometry g{};
+        g.mode = adapt::MODE_GEMM; g.M = M; g.N = h->N; g.Cin = h->Cin; g.taps = 1; g.kw = 1;
+        g.H = 1; g.W = 1; g.Wo = 1; g.HoWo = 1; g.sh = g.sw = g.dh = g.dw = 1; g.ph = g.pw = 0;
+        g.kstride = 1; g.img_stride = h->Cin;
+        return run_rows(h->lut, q, nullptr, out, g, s, h->wofs_dev, h->wofs_npad, &io);
+    }
+    return lines_linear(h->bits, h->storage, shape_of(h), h->dt_dev, nullptr, out, M, s, &h->ws, &io);
+}
+
+int adapt_conv2d_layer_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W, int stride_h, int stride_w,
+                           int pad_h, int pad_w, int dil_h, int dil_w, float s_x, float s_out, const float *bias_dev, int act,
+                           void *stream) {
+    const char *who = "adapt_conv2d_layer_f32";
+    int rc = check_weights(h, 1, who);
+    if (rc) return rc;
+    if (N < 0 || H < 1 || W < 1 || stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0 || dil_h < 1 || dil_w < 1)
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
+    const long long eh = (long long)H + 2LL * pad_h - (long long)dil_h * (h->kh - 1) - 1;
+    const long long ew = (long long)W + 2LL * pad_w - (long long)dil_w * (h->kw - 1) - 1;
+    if (eh < 0 || ew < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: filter larger than padded input", who);
+    const long long Ho = eh / stride_h + 1, Wo = ew / stride_w + 1;
+    if (N == 0) return ADAPT_OK;
+    LayerIO io;
+    if ((rc = layer_io(&io, h, x_dev, y_dev, s_x, s_out, bias_dev, act, who))) return rc;
+    const long long xt_bytes = (long long)N * (H + 2LL * pad_h) * (W + 2LL * pad_w) * h->Cp;
+    if (xt_bytes >= 0x7fffff00LL || (long long)N * h->N * Ho * Wo > 0x7fffffffLL || (long long)N * Ho * Wo > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
+    return lines_conv2d(h->bits, h->storage, shape_of(h), h->dt_dev, nullptr, reinterpret_cast<int32_t *>(y_dev), N, H, W, (int)Ho,
+                        (int)Wo, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream, &h->ws, &io);
+}
+
+int adapt_conv_transpose2d_layer_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W, int pad, float s_x,
+                                     float s_out, const float *bias_dev, int act, void *stream) {
+    const char *who = "adapt_conv_transpose2d_layer_f32";
+    int rc = check_weights(h, 2, who);
+    if (rc) return rc;
+    if (N < 0 || H < 1 || W < 1 || pad < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
+    const long long Ho = ((long long)H - 1) * h->stride - 2LL * pad + h->kh, Wo = ((long long)W - 1) * h->stride - 2LL * pad + h->kw;
+    if (Ho < 1 || Wo < 1) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: empty output", who);
+    if (N == 0) return ADAPT_OK;
+    LayerIO io;
+    if ((rc = layer_io(&io, h, x_dev, y_dev, s_x, s_out, bias_dev, act, who))) return rc;
+    if ((long long)N * h->N * Ho * Wo > 0x7fffffffLL || (long long)N * h->Cin * H * W > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
+    hipStream_t s = (hipStream_t)stream;
+    int32_t *out = reinterpret_cast<int32_t *>(y_dev);
+    if (h->phased && convt_phases_ok(H, W, h->kh, h->kw, h->stride, pad)) {
+        LinesShape q = convt_phase_shape(h->bits, h->N, h->Cin, h->kh, h->kw, h->stride);
+        const long long xt_bytes = (long long)N * (H + 2LL * (q.kh - 1)) * (W + 2LL * (q.kw - 1)) * q.Cp;
+        if (xt_bytes < 0x7fffff00LL)
+            return lines_conv_transpose2d(h->bits, h->storage, q, h->dt_dev, h->zsum_dev, nullptr, out, N, H, W, h->kh, h->kw, h->stride,
+                                          pad, s, &h->ws, &io);
+    }
+    int8_t *q8 = nullptr;
+    if ((rc = quantize_into_ws(h, io, (size_t)N * h->Cin * H * W, s, &q8))) return rc;
+    return convt_rows(h->lut, q8, h->w8_dev, out, N, h->Cin, H, W, h->N, h->kh, h->kw, h->stride, pad, s, h, &io);
 }
 
 /* ------------------------------------------------------------------ fp32 operations between layers */

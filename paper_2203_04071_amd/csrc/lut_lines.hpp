@@ -27,6 +27,8 @@
 
 #include <type_traits>
 
+#include "elementwise.hpp"
+
 namespace adapt {
 
 constexpr int LINES_THREADS = 1024;
@@ -56,10 +58,25 @@ struct LinesParams {
     // derived tables, window origin in xt and interleaved output positions; up to 4 of them share one launch.
     // Workgroup order: n-tile fastest, then row tile, then phase.
     int phases, m_tiles;
+    // Fused rescaling (single-pass tables only): when deq != 0 the output buffer receives fp32
+    //   y = float(acc) * scale, then + bias[n] if bias, then max(y, 0) if act == 1
+    // (the operations of dequant_kernel and relu_kernel, each rounded separately) instead of the int32 sums.
+    int deq, act;
+    float scale;
+    const float *bias;
     int xt_off[4];          // bytes into xt
     int out_off[4];         // elements into an output plane
     long long dt_off[4];    // 16-byte units into dt
 };
+
+// what is stored for the finished sum v of output channel n (see LinesParams::deq)
+__device__ __forceinline__ uint32_t finish_sum(const LinesParams &p, uint32_t v, int n) {
+    if (!p.deq) return v;
+    float y = (float)(int32_t)v * p.scale;
+    if (p.bias) y = y + p.bias[n];
+    if (p.act == 1) y = y > 0.0f ? y : 0.0f;
+    return __float_as_uint(y);
+}
 
 // per-phase launch parameters without indexing the by-value argument block dynamically
 template <typename T>
@@ -67,11 +84,24 @@ __device__ __forceinline__ T pick4(const T *v, int i) {
     return i == 0 ? v[0] : (i == 1 ? v[1] : (i == 2 ? v[2] : v[3]));
 }
 
+// Activation sources of the copy kernels: already quantised int8, or fp32 quantised on the fly with the quantiser of
+// quantize_kernel (Sec. III-A), so that a layer needs no separate quantisation pass.
+struct SrcI8 {
+    const int8_t *x;
+    __device__ __forceinline__ uint32_t byte(size_t i) const { return (uint32_t)(uint8_t)x[i]; }
+};
+struct SrcF32 {
+    const float *x;
+    float scale, Q;
+    __device__ __forceinline__ uint32_t byte(size_t i) const { return (uint32_t)quant1(x[i], scale, Q) & 0xffu; }
+};
+
 // NCHW int8 -> zero-padded copy, Cp (a multiple of 8) channels per pixel, in one of two orders:
 //   xmajor == 0: channel-last            [N][H + 2 ph][W + 2 pw][Cp]
 //   xmajor == 1: groups of four channels [N][H + 2 ph][Cp / 4][W + 2 pw][4]  (the four channel bytes of
 //                consecutive pixels are adjacent, so 4 rows x 4 channels of a lane are 16 contiguous bytes)
-__global__ void pad_channels_last_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ xt, int N, int C, int H,
+template <typename Src>
+__global__ void pad_channels_last_kernel(const Src x, int8_t *__restrict__ xt, int N, int C, int H,
                                          int W, int ph, int pw, int Cp, int xmajor) {
     const int Hp = H + 2 * ph, Wp = W + 2 * pw;
     const size_t total = (size_t)N * Hp * Wp * (Cp / 4);
@@ -90,7 +120,7 @@ __global__ void pad_channels_last_kernel(const int8_t *__restrict__ x, int8_t *_
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int c = c4 * 4 + q;
-                if (c < C) v |= (uint32_t)(uint8_t)x[(((size_t)n * C + c) * H + y) * W + xx] << (8 * q);
+                if (c < C) v |= x.byte((((size_t)n * C + c) * H + y) * W + xx) << (8 * q);
             }
         }
         if (xmajor) *reinterpret_cast<uint32_t *>(xt + i * 4) = v;
@@ -99,25 +129,26 @@ __global__ void pad_channels_last_kernel(const int8_t *__restrict__ x, int8_t *_
 }
 
 // [M][K] int8 -> [M][Kp] with zero fill, Kp a multiple of 32
-__global__ void pad_rows_kernel(const int8_t *__restrict__ a, int8_t *__restrict__ at, int M, int K, int Kp) {
+template <typename Src>
+__global__ void pad_rows_kernel(const Src a, int8_t *__restrict__ at, int M, int K, int Kp) {
     const size_t total = (size_t)M * Kp;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
         const int k = (int)(i % Kp);
         const size_t m = i / Kp;
-        at[i] = k < K ? a[m * K + k] : (int8_t)0;
+        at[i] = k < K ? (int8_t)a.byte(m * K + k) : (int8_t)0;
     }
 }
 
 // [M][K] int8 -> [Kp / 4][M][4]: for four consecutive inner indices the bytes of consecutive rows are adjacent (the
 // x-major order above with one image of one row), zero fill beyond K.  One workgroup of 256 threads moves a tile of
 // 64 rows x 64 inner indices through LDS so that both the reads (along K) and the writes (along M) coalesce.
-__global__ __launch_bounds__(256) void rows_to_xmajor_kernel(const int8_t *__restrict__ a, int8_t *__restrict__ at, int M, int K,
-                                                            int Kp) {
+template <typename Src>
+__global__ __launch_bounds__(256) void rows_to_xmajor_kernel(const Src a, int8_t *__restrict__ at, int M, int K, int Kp) {
     __shared__ uint32_t tile[16][65];
     const int m0 = blockIdx.x * 64, c0 = blockIdx.y * 16;      // c counts groups of four inner indices
     const int tid = threadIdx.x;
-    const bool fast = (K % 4 == 0) && ((reinterpret_cast<uintptr_t>(a) & 3u) == 0);
+    const bool fast = std::is_same<Src, SrcI8>::value && (K % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.x) & 3u) == 0);
 #pragma unroll
     for (int pass = 0; pass < 4; ++pass) {
         const int ml = pass * 16 + tid / 16, c = tid % 16;
@@ -125,11 +156,11 @@ __global__ __launch_bounds__(256) void rows_to_xmajor_kernel(const int8_t *__res
         uint32_t v = 0;
         if (m < M) {
             if (fast) {
-                if (k < K) v = *reinterpret_cast<const uint32_t *>(a + (size_t)m * K + k);
+                if (k < K) v = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const int8_t *>(a.x) + (size_t)m * K + k);
             } else {
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
-                    if (k + q < K) v |= (uint32_t)(uint8_t)a[(size_t)m * K + k + q] << (8 * q);
+                    if (k + q < K) v |= a.byte((size_t)m * K + k + q) << (8 * q);
             }
         }
         tile[c][ml] = v;
@@ -278,6 +309,21 @@ __global__ void convt_border_fix_kernel(int32_t *__restrict__ out, const int32_t
         }
         int32_t *q = out + ((size_t)plane * Ho + oy) * Wo + ox;
         *q = (int32_t)((uint32_t)*q - extra);
+    }
+}
+
+// In-place rescaling of a buffer of int32 sums into fp32 for the cases the product kernels cannot rescale themselves
+// (two-pass tables, transposed convolutions whose border terms are taken off afterwards, tanh outputs):
+// y = float(acc) * scale, + bias[c], then act (0 none, 1 max(y, 0), 2 tanh as in unary_kernel).
+__global__ __launch_bounds__(EW_THREADS) void finish_inplace_kernel(int32_t *__restrict__ buf, size_t n, size_t channels, size_t inner,
+                                                                    float scale, const float *__restrict__ bias, int act) {
+    const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
+        float y = (float)buf[i] * scale;
+        if (bias) y = y + bias[(i / inner) % channels];
+        if (act == 1) y = y > 0.0f ? y : 0.0f;
+        else if (act == 2) y = tanh_spec(y);
+        reinterpret_cast<float *>(buf)[i] = y;
     }
 }
 
@@ -523,7 +569,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_kernel(const LinesPar
                 const int img = r / p.HoWo, pix = r - img * p.HoWo;
                 const int a = pix / p.Wo, b = pix - a * p.Wo;
                 int32_t *q = p.out + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
-                if (p.shift < 0) *q = (int32_t)v;
+                if (p.shift < 0) *q = (int32_t)finish_sum(p, v, n);
                 else *q = (int32_t)((uint32_t)*q + (v << p.shift));
             }
         }
@@ -535,42 +581,84 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_kernel(const LinesPar
 // the one written (the compiler would hoist the LDS reads of the next step above the additions of
 // this one and run out of registers).
 //
-// row_add: wait until at most WAITN younger LDS reads are outstanding (then v has landed), then add
-// its eight 16-bit entries to eight accumulators: v_dot2 with the constant (1, 0) / (0, 1) extends one
-// half of a register and adds it in a single instruction.
-template <bool SIGNED, int WAITN>
-__device__ __forceinline__ void row_add(uint32_t *a, const u32x4_t &v) {
-    if (SIGNED) {
-        asm volatile("s_waitcnt lgkmcnt(%12)\n\t"
-                     "v_dot2c_i32_i16 %0, 1, %8\n\tv_dot2c_i32_i16 %1, 0x10000, %8\n\t"
-                     "v_dot2c_i32_i16 %2, 1, %9\n\tv_dot2c_i32_i16 %3, 0x10000, %9\n\t"
-                     "v_dot2c_i32_i16 %4, 1, %10\n\tv_dot2c_i32_i16 %5, 0x10000, %10\n\t"
-                     "v_dot2c_i32_i16 %6, 1, %11\n\tv_dot2c_i32_i16 %7, 0x10000, %11"
-                     : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
-                     : "v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w), "n"(WAITN));
+// The compiler takes the result of an asm statement to be complete when the statement ends, but the
+// LDS reads and global loads issued here land later.  Nothing it generates may touch such a register
+// before the wait that covers it, or a copy / spill would move stale data.  So these registers are
+// read-write operands of every statement that uses them (one live range, nothing to copy), and the
+// loop body contains no control flow the compiler can see: what depends on the position in the loop
+// (first group, last groups) is decided by scalar branches inside the asm statements.
+//
+// The conditions are handed over as plain loop arithmetic (groups left, step numbers) and compared inside the
+// statements: a boolean computed outside may come in a vector register, which a scalar operand cannot take.
+//
+// row_add: wait until at most WAITN younger LDS reads are outstanding (then v has landed; COND and `drain` == 0:
+// wait for all of them, for the group in which the younger reads are not issued), then add its eight
+// 16-bit entries to eight accumulators: v_dot2 with the constant (1, 0) / (0, 1) extends one half of a
+// register and adds it in a single instruction.
+template <bool SIGNED, int WAITN, bool COND = false>
+__device__ __forceinline__ void row_add(uint32_t *a, u32x4_t &v, uint32_t drain = 1) {
+#define ADAPT_DRAIN_ "s_cmp_lg_u32 %[dr], 0\n\ts_cbranch_scc1 .Lra_%=\n\ts_waitcnt lgkmcnt(0)\n.Lra_%=:\n\t"
+#define ADAPT_SDOTS_                                                                             \
+    "s_waitcnt lgkmcnt(%[wn])\n\t"                                                               \
+    "v_dot2c_i32_i16 %0, 1, %[x]\n\tv_dot2c_i32_i16 %1, 0x10000, %[x]\n\t"                      \
+    "v_dot2c_i32_i16 %2, 1, %[y]\n\tv_dot2c_i32_i16 %3, 0x10000, %[y]\n\t"                      \
+    "v_dot2c_i32_i16 %4, 1, %[z]\n\tv_dot2c_i32_i16 %5, 0x10000, %[z]\n\t"                      \
+    "v_dot2c_i32_i16 %6, 1, %[w]\n\tv_dot2c_i32_i16 %7, 0x10000, %[w]"
+#define ADAPT_UDOTS_                                                                             \
+    "s_waitcnt lgkmcnt(%[wn])\n\t"                                                               \
+    "v_dot2_u32_u16 %0, %[x], %[lo], %0\n\tv_dot2_u32_u16 %1, %[x], %[hi], %1\n\t"              \
+    "v_dot2_u32_u16 %2, %[y], %[lo], %2\n\tv_dot2_u32_u16 %3, %[y], %[hi], %3\n\t"              \
+    "v_dot2_u32_u16 %4, %[z], %[lo], %4\n\tv_dot2_u32_u16 %5, %[z], %[hi], %5\n\t"              \
+    "v_dot2_u32_u16 %6, %[w], %[lo], %6\n\tv_dot2_u32_u16 %7, %[w], %[hi], %7"
+#define ADAPT_ACC_ "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
+    if constexpr (SIGNED) {
+        if constexpr (COND)
+            asm volatile(ADAPT_DRAIN_ ADAPT_SDOTS_
+                         : ADAPT_ACC_
+                         : [x] "v"(v.x), [y] "v"(v.y), [z] "v"(v.z), [w] "v"(v.w), [wn] "n"(WAITN), [dr] "s"(drain)
+                         : "scc");
+        else
+            asm volatile(ADAPT_SDOTS_ : ADAPT_ACC_ : [x] "v"(v.x), [y] "v"(v.y), [z] "v"(v.z), [w] "v"(v.w), [wn] "n"(WAITN));
     } else {
         const uint32_t c_lo = 0x00000001u, c_hi = 0x00010000u;
-        asm volatile("s_waitcnt lgkmcnt(%12)\n\t"
-                     "v_dot2_u32_u16 %0, %8, %13, %0\n\tv_dot2_u32_u16 %1, %8, %14, %1\n\t"
-                     "v_dot2_u32_u16 %2, %9, %13, %2\n\tv_dot2_u32_u16 %3, %9, %14, %3\n\t"
-                     "v_dot2_u32_u16 %4, %10, %13, %4\n\tv_dot2_u32_u16 %5, %10, %14, %5\n\t"
-                     "v_dot2_u32_u16 %6, %11, %13, %6\n\tv_dot2_u32_u16 %7, %11, %14, %7"
-                     : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
-                     : "v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w), "n"(WAITN), "v"(c_lo), "v"(c_hi));
+        if constexpr (COND)
+            asm volatile(ADAPT_DRAIN_ ADAPT_UDOTS_
+                         : ADAPT_ACC_
+                         : [x] "v"(v.x), [y] "v"(v.y), [z] "v"(v.z), [w] "v"(v.w), [wn] "n"(WAITN), [lo] "v"(c_lo), [hi] "v"(c_hi),
+                           [dr] "s"(drain)
+                         : "scc");
+        else
+            asm volatile(ADAPT_UDOTS_
+                         : ADAPT_ACC_
+                         : [x] "v"(v.x), [y] "v"(v.y), [z] "v"(v.z), [w] "v"(v.w), [wn] "n"(WAITN), [lo] "v"(c_lo), [hi] "v"(c_hi));
     }
+#undef ADAPT_DRAIN_
+#undef ADAPT_SDOTS_
+#undef ADAPT_UDOTS_
+#undef ADAPT_ACC_
 }
 
 // row_fetch: activation = `bits`-wide field at bit SHIFT of word; read the 16 bytes of this lane's
 // column in that activation's line.  col = LDS address of the column in line 0 of table buffer 0 or 2,
-// OFF = 0 or 32768 selects the buffer after it.
-template <int SHIFT, int OFF>
-__device__ __forceinline__ void row_fetch(u32x4_t &v, uint32_t word, uint32_t bits, uint32_t col) {
+// OFF = 0 or 32768 selects the buffer after it.  COND: nothing is issued when on == 0.
+template <int SHIFT, int OFF, bool COND = false>
+__device__ __forceinline__ void row_fetch(u32x4_t &v, uint32_t word, uint32_t bits, uint32_t col, uint32_t on = 1) {
     uint32_t tmp;
-    asm volatile("v_bfe_u32 %1, %2, %3, %4\n\t"
-                 "v_lshl_add_u32 %1, %1, 7, %5\n\t"
-                 "ds_read_b128 %0, %1 offset:%6"
-                 : "=v"(v), "=&v"(tmp)
-                 : "v"(word), "n"(SHIFT), "s"(bits), "v"(col), "n"(OFF));
+    if constexpr (COND)
+        asm volatile("s_cmp_eq_u32 %[on], 0\n\ts_cbranch_scc1 .Lrf_%=\n\t"
+                     "v_bfe_u32 %[t], %[wd], %[sh], %[bits]\n\t"
+                     "v_lshl_add_u32 %[t], %[t], 7, %[col]\n\t"
+                     "ds_read_b128 %[v], %[t] offset:%[off]\n"
+                     ".Lrf_%=:"
+                     : [v] "+v"(v), [t] "=&v"(tmp)
+                     : [wd] "v"(word), [sh] "n"(SHIFT), [bits] "s"(bits), [col] "v"(col), [off] "n"(OFF), [on] "s"(on)
+                     : "scc");
+    else
+        asm volatile("v_bfe_u32 %[t], %[wd], %[sh], %[bits]\n\t"
+                     "v_lshl_add_u32 %[t], %[t], 7, %[col]\n\t"
+                     "ds_read_b128 %[v], %[t] offset:%[off]"
+                     : [v] "+v"(v), [t] "=&v"(tmp)
+                     : [wd] "v"(word), [sh] "n"(SHIFT), [bits] "s"(bits), [col] "v"(col), [off] "n"(OFF));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -629,17 +717,32 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     // table copy geometry: 8-bit tables take two operations of 64 lanes per wave, smaller tables one
     // operation of table_u4 / 16 lanes per wave
     const int lanes_act = TWO_OPS ? 64 : (table_u4 >> 4);
-    const bool dma_lane = TWO_OPS || lane < lanes_act;
+    const uint64_t dma_mask = lanes_act >= 64 ? ~0ull : ((1ull << lanes_act) - 1ull);
     const uint32_t dma_voff = (uint32_t)(wave * lanes_act + lane) * 16u;
     const uint32_t lds_tbl = (uint32_t)(uintptr_t)(lds_void_ptr)tbl;
     const uint32_t lds_wave = lds_tbl + (uint32_t)(wave * lanes_act) * 16u;
+    // table `step` -> buffer `buf`, only if step < steps (decided inside the statement, see row_add)
     auto dma = [&](int step, int buf) {
         const unsigned char *src = dt + (size_t)(unsigned)step * table_bytes;
         const uint32_t m0v = lds_wave + (uint32_t)buf * (TABLE_U4_MAX * 16u);
-        if (dma_lane) {
-            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(dma_voff), "s"(src), "s"(m0v) : "memory", "m0");
-            if (TWO_OPS)
-                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(dma_voff), "s"(src + 16384), "s"(m0v + 16384u) : "memory", "m0");
+        if constexpr (TWO_OPS) {
+            asm volatile("s_cmp_ge_i32 %[st], %[ns]\n\ts_cbranch_scc1 .Ldma_%=\n\t"
+                         "s_mov_b32 m0, %[ma]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[vo], %[sa]\n\t"
+                         "s_mov_b32 m0, %[mb]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[vo], %[sb]\n"
+                         ".Ldma_%=:"
+                         :
+                         : [st] "s"(step), [ns] "s"(steps), [vo] "v"(dma_voff), [sa] "s"(src), [sb] "s"(src + 16384), [ma] "s"(m0v), [mb] "s"(m0v + 16384u)
+                         : "memory", "m0", "scc");
+        } else {
+            uint64_t save;
+            asm volatile("s_cmp_ge_i32 %[st], %[ns]\n\ts_cbranch_scc1 .Ldma_%=\n\t"
+                         "s_mov_b64 %[sv], exec\n\ts_mov_b64 exec, %[mk]\n\t"
+                         "s_mov_b32 m0, %[ma]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[vo], %[sa]\n\t"
+                         "s_mov_b64 exec, %[sv]\n"
+                         ".Ldma_%=:"
+                         : [sv] "=&s"(save)
+                         : [st] "s"(step), [ns] "s"(steps), [vo] "v"(dma_voff), [sa] "s"(src), [ma] "s"(m0v), [mk] "s"(dma_mask)
+                         : "memory", "m0", "scc");
         }
     };
 
@@ -661,30 +764,42 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
         }
         if (REGULAR) row_step = p.HoWo == 1 ? (uint32_t)p.img_stride : (uint32_t)p.ox_stride;
     }
-    // activations of a group of four steps: element i of the register block = row i, one byte per step
-    constexpr int AQ = (R + 3) / 4;
-    auto load_acts = [&](u32x4_t *a, const int8_t *xrow) {
-        if (XMAJOR) {       // 4 consecutive pixels x 4 channel bytes are 16 contiguous bytes
-            asm volatile("global_load_dwordx4 %0, %2, %4\n\tglobal_load_dwordx4 %1, %3, %4"
-                         : "=&v"(a[0]), "=&v"(a[AQ - 1])
-                         : "v"(base[0]), "v"(base[NB - 1]), "s"(xrow));
-            return;
-        }
+    // Activations of a group of four steps, one register per row (one byte per step).  XMAJOR: two 16-byte loads
+    // into two register quadruples; else one 4-byte load per row.  Nothing is issued when on == 0.
+    struct Acts {
+        u32x4_t q[XMAJOR ? 2 : 1];
+        uint32_t w[XMAJOR ? 1 : R];
+        __device__ __forceinline__ uint32_t row(int i) const { return XMAJOR ? q[i / 4][i % 4] : w[i]; }
+    };
+    auto load_acts = [&](Acts &a, uint32_t on, const int8_t *xrow) {
+        if constexpr (XMAJOR) {     // 4 consecutive pixels x 4 channel bytes are 16 contiguous bytes
+            asm volatile("s_cmp_eq_u32 %[on], 0\n\ts_cbranch_scc1 .Lla_%=\n\t"
+                         "global_load_dwordx4 %[a0], %[b0], %[xr]\n\tglobal_load_dwordx4 %[a1], %[b1], %[xr]\n"
+                         ".Lla_%=:"
+                         : [a0] "+v"(a.q[0]), [a1] "+v"(a.q[1])
+                         : [b0] "v"(base[0]), [b1] "v"(base[NB - 1]), [xr] "s"(xrow), [on] "s"(on)
+                         : "scc");
+        } else {
 #pragma unroll
-        for (int i = 0; i < R; ++i) {
-            uint32_t w;
-            if (REGULAR) {
-                const int8_t *srow = xrow + (size_t)i * row_step;
-                asm volatile("global_load_dword %0, %1, %2" : "=v"(w) : "v"(base[0]), "s"(srow));
-            } else {
-                asm volatile("global_load_dword %0, %1, %2" : "=v"(w) : "v"(base[i]), "s"(xrow));
+            for (int i = 0; i < R; ++i) {
+                const int8_t *srow = REGULAR ? xrow + (size_t)i * row_step : xrow;
+                asm volatile("s_cmp_eq_u32 %[on], 0\n\ts_cbranch_scc1 .Lla_%=\n\t"
+                             "global_load_dword %[a0], %[b0], %[xr]\n"
+                             ".Lla_%=:"
+                             : [a0] "+v"(a.w[i])
+                             : [b0] "v"(base[REGULAR ? 0 : i]), [xr] "s"(srow), [on] "s"(on)
+                             : "scc");
             }
-            a[i / 4][i % 4] = w;
         }
     };
-    auto tie = [&](u32x4_t *a) {
-#pragma unroll
-        for (int q = 0; q < AQ; ++q) asm volatile("" : "+v"(a[q]));
+    // end of a step: wait until at most IMM's count of this wave's memory operations are outstanding (all of them when
+    // at most one more group follows: the schedule of the last two groups is incomplete), then meet the other waves
+    auto step_end = [&](uint32_t rem, auto imm) {
+        asm volatile("s_cmp_gt_u32 %[dr], 1\n\ts_cbranch_scc1 .Lse_%=\n\ts_waitcnt vmcnt(0)\n.Lse_%=:\n\t"
+                     "s_waitcnt %[im]\n\ts_barrier"
+                     :
+                     : [dr] "s"(rem), [im] "n"(decltype(imm)::value)
+                     : "memory", "scc");
     };
 
     uint32_t acc[R * 8];
@@ -706,75 +821,70 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
         }
     };
 
-    // prologue: tables of steps 0..2, activations of group 0
-    dma(0, 0);
-    if (steps > 1) dma(1, 1);
-    if (steps > 2) dma(2, 2);
-    u32x4_t aw[AQ], awn[AQ];
+    Acts aw, awn;
 #pragma unroll
-    for (int q = 0; q < AQ; ++q) { aw[q] = u32x4_t{0, 0, 0, 0}; awn[q] = u32x4_t{0, 0, 0, 0}; }
-    load_acts(aw, xt);
-    __builtin_amdgcn_s_waitcnt(WAIT_ALL);
-    __builtin_amdgcn_s_barrier();
-    tie(aw);
-    advance_group();
-
+    for (int q = 0; q < (XMAJOR ? 2 : 1); ++q) { aw.q[q] = u32x4_t{0, 0, 0, 0}; awn.q[q] = u32x4_t{0, 0, 0, 0}; }
+#pragma unroll
+    for (int i = 0; i < (XMAJOR ? 1 : R); ++i) { aw.w[i] = 0; awn.w[i] = 0; }
+    constexpr int H = R / 2;                // rows per half
+    constexpr int WN = H - 1;               // younger LDS reads that may be in flight when a row is added
+    u32x4_t rv[H];
+#pragma unroll
+    for (int i = 0; i < H; ++i) rv[i] = u32x4_t{0, 0, 0, 0};
     const uint32_t ubits = (uint32_t)p.bits;
     // LDS address of this lane's column in table buffers 0 and 2 (buffers 1 and 3 lie 32768 bytes after them)
     const uint32_t cb0 = lds_tbl + (uint32_t)j * 16u;
     const uint32_t cb2 = cb0 + 2u * (TABLE_U4_MAX * 16u);
-    constexpr int H = R / 2;                // rows per half
-    constexpr int WN = H - 1;               // younger LDS reads that may be in flight when a row is added
-    u32x4_t rv[H];
+
+    // prologue: tables of steps 0..2, activations of group 0
+    dma(0, 0);
+    dma(1, 1);
+    dma(2, 2);
+    load_acts(aw, 1u, xt);
+    step_end(0u, std::integral_constant<int, WAIT_ALL>{});
+    advance_group();
     // first-half entries of step 0
 #pragma unroll
-    for (int i = 0; i < H; ++i) row_fetch<0, 0>(rv[i], aw[i / 4][i % 4], ubits, cb0);
+    for (int i = 0; i < H; ++i) row_fetch<0, 0>(rv[i], aw.row(i), ubits, cb0);
 
     for (int g = 0; g < groups; ++g) {
         const int s0 = g << 2;
-        const bool last = g == groups - 1;
-        const bool tail = g >= groups - 2;      // not every operation of the steady-state schedule is issued
+        const uint32_t rem = (uint32_t)(groups - 1 - g);        // groups that follow this one
         // u = 0: table buffers 0 (this step) and 1 (next step)
-        if (s0 + 3 < steps) dma(s0 + 3, 3);
-        if (!last) load_acts(awn, xt + tapoff + t4off);
+        dma(s0 + 3, 3);
+        load_acts(awn, rem, xt + tapoff + t4off);
 #pragma unroll
-        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<0, 0>(rv[i], aw[(H + i) / 4][(H + i) % 4], ubits, cb0); }
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<0, 0>(rv[i], aw.row(H + i), ubits, cb0); }
 #pragma unroll
-        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<8, 32768>(rv[i], aw[i / 4][i % 4], ubits, cb0); }
-        if (tail) __builtin_amdgcn_s_waitcnt(WAIT_ALL); else __builtin_amdgcn_s_waitcnt(WAIT_DA);
-        __builtin_amdgcn_s_barrier();
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<8, 32768>(rv[i], aw.row(i), ubits, cb0); }
+        step_end(rem, std::integral_constant<int, WAIT_DA>{});
         // u = 1: buffers 1 and 2
-        if (s0 + 4 < steps) dma(s0 + 4, 0);
+        dma(s0 + 4, 0);
 #pragma unroll
-        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<8, 32768>(rv[i], aw[(H + i) / 4][(H + i) % 4], ubits, cb0); }
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<8, 32768>(rv[i], aw.row(H + i), ubits, cb0); }
 #pragma unroll
-        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<16, 0>(rv[i], aw[i / 4][i % 4], ubits, cb2); }
-        if (tail) __builtin_amdgcn_s_waitcnt(WAIT_ALL); else __builtin_amdgcn_s_waitcnt(WAIT_DA);
-        __builtin_amdgcn_s_barrier();
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<16, 0>(rv[i], aw.row(i), ubits, cb2); }
+        step_end(rem, std::integral_constant<int, WAIT_DA>{});
         // u = 2: buffers 2 and 3
-        if (s0 + 5 < steps) dma(s0 + 5, 1);
+        dma(s0 + 5, 1);
 #pragma unroll
-        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<16, 0>(rv[i], aw[(H + i) / 4][(H + i) % 4], ubits, cb2); }
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<16, 0>(rv[i], aw.row(H + i), ubits, cb2); }
 #pragma unroll
-        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<24, 32768>(rv[i], aw[i / 4][i % 4], ubits, cb2); }
-        if (tail) __builtin_amdgcn_s_waitcnt(WAIT_ALL); else __builtin_amdgcn_s_waitcnt(WAIT_D);
-        __builtin_amdgcn_s_barrier();
-        tie(awn);
-        // u = 3: buffers 3 and 0; the second-half fetches are the first rows of the next group's first step
-        if (s0 + 6 < steps) dma(s0 + 6, 2);
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<24, 32768>(rv[i], aw.row(i), ubits, cb2); }
+        step_end(rem, std::integral_constant<int, WAIT_D>{});
+        // u = 3: buffers 3 and 0; the second-half fetches are the first rows of the next group's first step (awn has
+        // landed: the wait that ended u = 2 covers it).  In the last group they are not issued, so every addition of
+        // that half waits for all outstanding reads.
+        dma(s0 + 6, 2);
 #pragma unroll
-        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<24, 32768>(rv[i], aw[(H + i) / 4][(H + i) % 4], ubits, cb2); }
-        if (!last) {
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<24, 32768>(rv[i], aw.row(H + i), ubits, cb2); }
 #pragma unroll
-            for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<0, 0>(rv[i], awn[i / 4][i % 4], ubits, cb0); }
-        } else {
-#pragma unroll
-            for (int i = 0; i < H; ++i) row_add<SIGNED, 0>(acc + (H + i) * 8, rv[i]);
+        for (int i = 0; i < H; ++i) {
+            row_add<SIGNED, WN, true>(acc + (H + i) * 8, rv[i], rem);
+            row_fetch<0, 0, true>(rv[i], awn.row(i), ubits, cb0, rem);
         }
-        if (tail) __builtin_amdgcn_s_waitcnt(WAIT_ALL); else __builtin_amdgcn_s_waitcnt(WAIT_D);
-        __builtin_amdgcn_s_barrier();
-#pragma unroll
-        for (int q = 0; q < AQ; ++q) aw[q] = awn[q];
+        step_end(rem, std::integral_constant<int, WAIT_D>{});
+        aw = awn;
         advance_group();
     }
 
@@ -801,6 +911,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
                 v[i] = acc[i * 8];
 #pragma unroll
                 for (int c = 1; c < 8; ++c) v[i] = (j == c) ? acc[i * 8 + c] : v[i];
+                if (p.shift < 0) v[i] = finish_sum(p, v[i], n);
             }
 #pragma unroll
             for (int hq = 0; hq < 2; ++hq) {
@@ -834,7 +945,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
                     else { img = r / p.HoWo; pix = r - img * p.HoWo; }
                     const int a = pix / p.Wo, b = pix - a * p.Wo;
                     int32_t *q = p.out + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
-                    if (p.shift < 0) *q = (int32_t)v;
+                    if (p.shift < 0) *q = (int32_t)finish_sum(p, v, n);
                     else *q = (int32_t)((uint32_t)*q + (v << p.shift));
                 }
             }

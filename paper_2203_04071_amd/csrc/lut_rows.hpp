@@ -41,7 +41,20 @@ struct RowsParams {
     int a_zero2, a_skip2;   // byte offset in a table row of activation 0 / of the all-zero column
     int MT, KS;             // rows per workgroup, K slices per workgroup; MT * KS == ROWS_THREADS
     int shift;              // < 0: out = acc;  >= 0: out += acc << shift (second half of a split table)
+    // fused rescaling (single-pass tables only): deq != 0 stores fp32 y = float(acc) * scale, + bias[n] if bias, then
+    // max(y, 0) if act == 1, each operation rounded separately, instead of the int32 sum
+    int deq, act;
+    float scale;
+    const float *bias;
 };
+
+__device__ __forceinline__ uint32_t finish_sum(const RowsParams &p, uint32_t v, int n) {
+    if (!p.deq) return v;
+    float y = (float)(int32_t)v * p.scale;
+    if (p.bias) y = y + p.bias[n];
+    if (p.act == 1) y = y > 0.0f ? y : 0.0f;
+    return __float_as_uint(y);
+}
 
 // weights -> byte offsets of their table rows, in the order the kernel walks K
 __global__ void pack_row_offsets_kernel(const int8_t *__restrict__ w, uint32_t *__restrict__ wofs, int Ktot,
@@ -191,7 +204,7 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
             for (int n = 0; n < NT; ++n) {
                 if (n0 + n < p.N) {
                     int32_t *q = o + (size_t)(n0 + n) * p.HoWo;
-                    if (p.shift < 0) *q = (int32_t)acc[n];
+                    if (p.shift < 0) *q = (int32_t)finish_sum(p, acc[n], n0 + n);
                     else *q = (int32_t)((uint32_t)*q + (acc[n] << p.shift));
                 }
             }
@@ -213,7 +226,7 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
         for (int j = 0; j < p.KS; ++j) s += red[((size_t)j * NT + n) * p.MT + r];
         const int img2 = m2 / p.HoWo, pix2 = m2 - img2 * p.HoWo;
         int32_t *q = p.out + (size_t)img2 * p.N * p.HoWo + (size_t)(n0 + n) * p.HoWo + pix2;
-        if (p.shift < 0) *q = (int32_t)s;
+        if (p.shift < 0) *q = (int32_t)finish_sum(p, s, n0 + n);
         else *q = (int32_t)((uint32_t)*q + (s << p.shift));
     }
 }

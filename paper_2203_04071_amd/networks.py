@@ -78,26 +78,33 @@ class ResNet20:
         self.scales = None
         self.macs = None
 
-    def _conv(self, i, x, used, keep):
+    def _conv(self, i, x, used, keep, relu=False):
+        """conv (+ ReLU).  Once the scales are frozen and nobody asks for the integer sums, the layer runs as one
+        fused call (quantise while laying out the input, rescale + ReLU inside the product kernel)."""
         bits = self.bits
+        st = self.plan[i][2]
+        if self.scales is not None and keep is None:
+            s_x = self.scales[i]
+            used.append(s_x)
+            return B.adapt_conv2d_layer_f32(self.pws[i], x, s_x, _f(s_x) * _f(self.qws[i][1]), (st, st), (1, 1),
+                                            act=B.ACT_RELU if relu else B.ACT_NONE)
         s_x = calibrated_scale(x, bits) if self.scales is None else self.scales[i]
         used.append(s_x)
         qx = B.adapt_quantize_f32(x, s_x, bits)
-        st = self.plan[i][2]
         acc = B.adapt_approx_conv2d_packed(self.pws[i], qx, (st, st), (1, 1))
         if keep is not None:
             keep.append(acc)
         n, c, h, w = acc.shape
-        return B.adapt_dequant_i32(acc, _f(s_x) * _f(self.qws[i][1]), n, c, h * w)
+        y = B.adapt_dequant_i32(acc, _f(s_x) * _f(self.qws[i][1]), n, c, h * w)
+        return B.adapt_relu_f32(y, out=y) if relu else y
 
     def forward(self, x, keep=None):
         used = []
-        x = B.adapt_relu_f32(self._conv(0, x, used, keep))
+        x = self._conv(0, x, used, keep, relu=True)
         i = 1
         while i < len(self.plan):
             cin, cout, stride = self.plan[i]
-            y = self._conv(i, x, used, keep)
-            B.adapt_relu_f32(y, out=y)
+            y = self._conv(i, x, used, keep, relu=True)
             z = self._conv(i + 1, y, used, keep)
             sc = x if (stride == 1 and cin == cout) else B.adapt_shortcut_a_f32(x, cout)
             x = B.adapt_add_f32(z, sc, relu=True)
@@ -105,6 +112,9 @@ class ResNet20:
         pooled = B.adapt_avgpool_hw_f32(x)
         s_p = calibrated_scale(pooled, self.bits) if self.scales is None else self.scales[len(self.plan)]
         used.append(s_p)
+        if self.scales is not None and keep is None:
+            logits = B.adapt_linear_layer_f32(self.p_fw, pooled, s_p, _f(s_p) * _f(self.s_fw), self.fc_b)
+            return dict(logits=logits, fc_acc=None, feat=x, scales=used)
         qp = B.adapt_quantize_f32(pooled, s_p, self.bits)
         acc = B.adapt_approx_linear_packed(self.p_fw, qp)
         logits = B.adapt_dequant_i32(acc, _f(s_p) * _f(self.s_fw), acc.shape[0], acc.shape[1], 1, self.fc_b)
@@ -165,6 +175,12 @@ class DCGAN:
         nl = len(self.plan)
         acc = None
         for i, (cin, cout, s, p) in enumerate(self.plan):
+            if self.scales is not None and keep is None:        # frozen scales: one fused call per layer
+                s_x = self.scales[i]
+                used.append(s_x)
+                x = B.adapt_conv_transpose2d_layer_f32(self.pws[i], x, s_x, _f(s_x) * _f(self.qws[i][1]), p,
+                                                       act=B.ACT_TANH if i == nl - 1 else B.ACT_RELU)
+                continue
             s_x = calibrated_scale(x, self.bits) if self.scales is None else self.scales[i]
             used.append(s_x)
             qx = B.adapt_quantize_f32(x, s_x, self.bits)

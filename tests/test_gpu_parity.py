@@ -338,8 +338,10 @@ def test_config3_resnet20_full_size(B):
         assert (host(g) == o).all(), f"conv {i}"
     assert (host(got["fc_acc"]) == want["fc_acc"]).all()
     assert_f32_close(host(got["logits"]), want["logits"])
-    again = net.forward(dev(c["x"]))                       # frozen scales, no host reads
-    assert (host(again["fc_acc"]) == want["fc_acc"]).all()
+    again = net.forward(dev(c["x"]))                       # frozen scales: fused layer calls, no host reads
+    assert bits_equal(host(again["logits"]), host(got["logits"]))
+    assert bits_equal(host(again["feat"]), host(got["feat"]))
+    assert_f32_close(host(again["feat"]), want["feat"])
 
 
 def test_config4_lstm_full_size(B):
@@ -353,6 +355,7 @@ def test_config4_lstm_full_size(B):
     assert (host(got["acc_hh_last"]) == want["acc_hh_last"]).all()
     assert_f32_close(host(got["hs"]), want["hs"])
     assert_f32_close(host(got["c"]), want["c"])
+    assert bits_equal(host(got["hs"]), want["hs"])          # the written-out gate functions make this exact
 
 
 @pytest.mark.parametrize("bits", [6, 8])
@@ -362,17 +365,20 @@ def test_config5_dcgan_full_size(B, bits):
     th = orc.host_threads()
     want = onet.dcgan(c, threads=th, keep=True)
     keep = []
-    got = gnet.DCGAN(c).forward(dev(c["z"]), keep=keep)
+    net = gnet.DCGAN(c)
+    got = net.forward(dev(c["z"]), keep=keep)
     assert [np.float32(s) for s in got["scales"]] == [np.float32(s) for s in want["scales"]]
     for i, (g, o) in enumerate(zip(keep, want["accs"])):
         assert (host(g) == o).all(), f"layer {i}"
     assert_f32_close(host(got["out"]), want["out"])
+    again = net.forward(dev(c["z"]))                        # frozen scales: one fused call per layer
+    assert bits_equal(host(again["out"]), host(got["out"]))
 
 
 # ------------------------------------------------------------------ long-matrix ("lines") kernel via packed weights
 
 PACKED_LINEAR = [
-    # M, K, N  (the packed entry point always runs the long-matrix kernel, whatever M is)
+    # M, K, N  (short products take the whole-table kernel with pre-packed offsets, long ones the derived-table kernel)
     (1, 8, 1), (5, 9, 3), (127, 32, 8), (129, 40, 9), (1024, 64, 16), (1500, 100, 20), (3000, 33, 7),
     (4100, 96, 24), (9000, 17, 65),
 ]
@@ -583,3 +589,99 @@ def test_graph_replay_matches_eager(B):
         x2 = x * 0.75
         want2 = host(net.forward(x2)[key])
         assert bits_equal(host(cap.replay(x2)[key]), want2)
+
+
+# ------------------------------------------------------------------ whole layers (fp32 in, fp32 out)
+
+def _oracle_layer(acc, s_out, channels, inner, bias, act):
+    outer = acc.size // (channels * inner)
+    y = orc.dequant(acc, s_out, outer, channels, inner, bias)
+    if act == 1:
+        y = orc.relu(y)
+    elif act == 2:
+        y = orc.tanh(y)
+    return y.reshape(acc.shape)
+
+
+LAYER_LINEAR = [(37, 24, 10), (4096, 32, 16), (4101, 100, 9), (8192, 40, 256), (64, 512, 64)]
+
+
+@pytest.mark.parametrize("kind", ["b8", "b6", "b5wide"])
+@pytest.mark.parametrize("shape", LAYER_LINEAR)
+def test_linear_layer_f32(B, kind, shape):
+    M, K, N = shape
+    bits = {"b8": 8, "b6": 6, "b5wide": 5}[kind]
+    rng = np.random.default_rng(M + K + N + bits)
+    lut = wl.make_lut(bits) if kind != "b5wide" else rng.integers(-2**31, 2**31 - 1, size=(32, 32), dtype=np.int64).astype(np.int32)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    W = wl.random_i8(rng, (N, K), bits)
+    bias = rng.standard_normal(N).astype(np.float32)
+    s_x = orc.scale_from_amax(orc.absmax(x), bits)
+    s_out = np.float32(s_x) * np.float32(0.013)
+    acc = orc.approx_linear(lut, bits, orc.quantize(x, s_x, bits), W, threads=8)
+    pw = B.adapt_weights_pack_linear(B.Lut(lut, bits), dev(W))
+    for b, act in ((None, 0), (bias, 1), (bias, 2)):
+        want = _oracle_layer(acc, s_out, N, 1, b, act)
+        got = host(B.adapt_linear_layer_f32(pw, dev(x), s_x, s_out, dev(b) if b is not None else None, act))
+        assert bits_equal(got, want), (b is not None, act)
+
+
+LAYER_CONV = [
+    # N, Cin, H, W, Cout, k, stride, pad
+    (2, 3, 8, 8, 4, 3, 1, 1),
+    (3, 16, 32, 32, 16, 3, 1, 1),
+    (2, 16, 32, 32, 32, 3, 2, 1),
+    (8, 64, 32, 32, 64, 3, 1, 1),
+    (5, 7, 13, 11, 19, 3, 1, 1),
+    (40, 32, 8, 8, 24, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("kind", ["b8", "b6", "b5wide"])
+@pytest.mark.parametrize("case", LAYER_CONV)
+def test_conv2d_layer_f32(B, kind, case):
+    N, Cin, H, W, Cout, k, st, pd = case
+    bits = {"b8": 8, "b6": 6, "b5wide": 5}[kind]
+    rng = np.random.default_rng(sum(case) + bits)
+    lut = wl.make_lut(bits) if kind != "b5wide" else rng.integers(-2**31, 2**31 - 1, size=(32, 32), dtype=np.int64).astype(np.int32)
+    x = rng.standard_normal((N, Cin, H, W)).astype(np.float32)
+    w = wl.random_i8(rng, (Cout, Cin, k, k), bits, "gauss")
+    bias = rng.standard_normal(Cout).astype(np.float32)
+    s_x = orc.scale_from_amax(orc.absmax(x), bits)
+    s_out = np.float32(s_x) * np.float32(0.02)
+    acc = orc.approx_conv2d(lut, bits, orc.quantize(x, s_x, bits), w, (st, st), (pd, pd), threads=8)
+    pw = B.adapt_weights_pack_conv2d(B.Lut(lut, bits), dev(w))
+    for b, act in ((None, 0), (bias, 1), (None, 2)):
+        want = _oracle_layer(acc, s_out, Cout, acc.shape[2] * acc.shape[3], b, act)
+        got = host(B.adapt_conv2d_layer_f32(pw, dev(x), s_x, s_out, (st, st), (pd, pd), (1, 1), dev(b) if b is not None else None, act))
+        assert bits_equal(got, want), (b is not None, act)
+
+
+LAYER_CONVT = [
+    (2, 8, 4, 4, 8, 4, 2, 1),
+    (3, 32, 8, 8, 16, 4, 2, 1),
+    (2, 64, 16, 16, 24, 4, 2, 1),
+    (2, 7, 5, 5, 5, 2, 2, 0),          # no border terms: rescaled inside the product kernel
+    (2, 3, 5, 3, 2, 3, 2, 0),          # plain form
+    (4, 10, 1, 1, 6, 4, 1, 0),         # single input pixel
+]
+
+
+@pytest.mark.parametrize("kind", ["b8", "b6", "b5wide"])
+@pytest.mark.parametrize("case", LAYER_CONVT)
+def test_conv_transpose2d_layer_f32(B, kind, case):
+    N, Cin, H, W, Cout, k, st, pd = case
+    bits = {"b8": 8, "b6": 6, "b5wide": 5}[kind]
+    rng = np.random.default_rng(sum(case) + bits)
+    lut = wl.make_lut(bits) if kind != "b5wide" else rng.integers(-2**31, 2**31 - 1, size=(32, 32), dtype=np.int64).astype(np.int32)
+    x = rng.standard_normal((N, Cin, H, W)).astype(np.float32)
+    w = wl.random_i8(rng, (Cin, Cout, k, k), bits, "gauss")
+    bias = rng.standard_normal(Cout).astype(np.float32)
+    s_x = orc.scale_from_amax(orc.absmax(x), bits)
+    s_out = np.float32(s_x) * np.float32(0.02)
+    acc = orc.approx_conv_transpose2d(lut, bits, orc.quantize(x, s_x, bits), w, st, pd, threads=8)
+    pw = B.adapt_weights_pack_conv_transpose2d(B.Lut(lut, bits), dev(w), st)
+    for b, act in ((None, 0), (bias, 1), (bias, 2)):
+        want = _oracle_layer(acc, s_out, Cout, acc.shape[2] * acc.shape[3], b, act)
+        got = host(B.adapt_conv_transpose2d_layer_f32(pw, dev(x), s_x, s_out, pd, dev(b) if b is not None else None, act))
+        assert bits_equal(got, want), (b is not None, act)
