@@ -584,81 +584,47 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_kernel(const LinesPar
 // The compiler takes the result of an asm statement to be complete when the statement ends, but the
 // LDS reads and global loads issued here land later.  Nothing it generates may touch such a register
 // before the wait that covers it, or a copy / spill would move stale data.  So these registers are
-// read-write operands of every statement that uses them (one live range, nothing to copy), and the
-// loop body contains no control flow the compiler can see: what depends on the position in the loop
-// (first group, last groups) is decided by scalar branches inside the asm statements.
+// read-write operands of every statement that uses them (one live range, nothing to copy), the loop
+// body contains no control flow at all (the same operations are issued in every group; past the end of
+// the matrix they fetch valid but unused data), and a final wait retires everything before the compiler
+// takes over again.  paper_2203_04071_amd/isa_check.py verifies the generated code.
 //
-// The conditions are handed over as plain loop arithmetic (groups left, step numbers) and compared inside the
-// statements: a boolean computed outside may come in a vector register, which a scalar operand cannot take.
-//
-// row_add: wait until at most WAITN younger LDS reads are outstanding (then v has landed; COND and `drain` == 0:
-// wait for all of them, for the group in which the younger reads are not issued), then add its eight
-// 16-bit entries to eight accumulators: v_dot2 with the constant (1, 0) / (0, 1) extends one half of a
-// register and adds it in a single instruction.
-template <bool SIGNED, int WAITN, bool COND = false>
-__device__ __forceinline__ void row_add(uint32_t *a, u32x4_t &v, uint32_t drain = 1) {
-#define ADAPT_DRAIN_ "s_cmp_lg_u32 %[dr], 0\n\ts_cbranch_scc1 .Lra_%=\n\ts_waitcnt lgkmcnt(0)\n.Lra_%=:\n\t"
-#define ADAPT_SDOTS_                                                                             \
-    "s_waitcnt lgkmcnt(%[wn])\n\t"                                                               \
-    "v_dot2c_i32_i16 %0, 1, %[x]\n\tv_dot2c_i32_i16 %1, 0x10000, %[x]\n\t"                      \
-    "v_dot2c_i32_i16 %2, 1, %[y]\n\tv_dot2c_i32_i16 %3, 0x10000, %[y]\n\t"                      \
-    "v_dot2c_i32_i16 %4, 1, %[z]\n\tv_dot2c_i32_i16 %5, 0x10000, %[z]\n\t"                      \
-    "v_dot2c_i32_i16 %6, 1, %[w]\n\tv_dot2c_i32_i16 %7, 0x10000, %[w]"
-#define ADAPT_UDOTS_                                                                             \
-    "s_waitcnt lgkmcnt(%[wn])\n\t"                                                               \
-    "v_dot2_u32_u16 %0, %[x], %[lo], %0\n\tv_dot2_u32_u16 %1, %[x], %[hi], %1\n\t"              \
-    "v_dot2_u32_u16 %2, %[y], %[lo], %2\n\tv_dot2_u32_u16 %3, %[y], %[hi], %3\n\t"              \
-    "v_dot2_u32_u16 %4, %[z], %[lo], %4\n\tv_dot2_u32_u16 %5, %[z], %[hi], %5\n\t"              \
-    "v_dot2_u32_u16 %6, %[w], %[lo], %6\n\tv_dot2_u32_u16 %7, %[w], %[hi], %7"
-#define ADAPT_ACC_ "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
+// row_add: wait until at most WAITN younger LDS reads are outstanding (then v has landed), then add
+// its eight 16-bit entries to eight accumulators: v_dot2 with the constant (1, 0) / (0, 1) extends one
+// half of a register and adds it in a single instruction.
+template <bool SIGNED, int WAITN>
+__device__ __forceinline__ void row_add(uint32_t *a, u32x4_t &v) {
     if constexpr (SIGNED) {
-        if constexpr (COND)
-            asm volatile(ADAPT_DRAIN_ ADAPT_SDOTS_
-                         : ADAPT_ACC_
-                         : [x] "v"(v.x), [y] "v"(v.y), [z] "v"(v.z), [w] "v"(v.w), [wn] "n"(WAITN), [dr] "s"(drain)
-                         : "scc");
-        else
-            asm volatile(ADAPT_SDOTS_ : ADAPT_ACC_ : [x] "v"(v.x), [y] "v"(v.y), [z] "v"(v.z), [w] "v"(v.w), [wn] "n"(WAITN));
+        asm volatile("s_waitcnt lgkmcnt(%[wn])\n\t"
+                     "v_dot2c_i32_i16 %0, 1, %[x]\n\tv_dot2c_i32_i16 %1, 0x10000, %[x]\n\t"
+                     "v_dot2c_i32_i16 %2, 1, %[y]\n\tv_dot2c_i32_i16 %3, 0x10000, %[y]\n\t"
+                     "v_dot2c_i32_i16 %4, 1, %[z]\n\tv_dot2c_i32_i16 %5, 0x10000, %[z]\n\t"
+                     "v_dot2c_i32_i16 %6, 1, %[w]\n\tv_dot2c_i32_i16 %7, 0x10000, %[w]"
+                     : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
+                     : [x] "v"(v.x), [y] "v"(v.y), [z] "v"(v.z), [w] "v"(v.w), [wn] "n"(WAITN));
     } else {
         const uint32_t c_lo = 0x00000001u, c_hi = 0x00010000u;
-        if constexpr (COND)
-            asm volatile(ADAPT_DRAIN_ ADAPT_UDOTS_
-                         : ADAPT_ACC_
-                         : [x] "v"(v.x), [y] "v"(v.y), [z] "v"(v.z), [w] "v"(v.w), [wn] "n"(WAITN), [lo] "v"(c_lo), [hi] "v"(c_hi),
-                           [dr] "s"(drain)
-                         : "scc");
-        else
-            asm volatile(ADAPT_UDOTS_
-                         : ADAPT_ACC_
-                         : [x] "v"(v.x), [y] "v"(v.y), [z] "v"(v.z), [w] "v"(v.w), [wn] "n"(WAITN), [lo] "v"(c_lo), [hi] "v"(c_hi));
+        asm volatile("s_waitcnt lgkmcnt(%[wn])\n\t"
+                     "v_dot2_u32_u16 %0, %[x], %[lo], %0\n\tv_dot2_u32_u16 %1, %[x], %[hi], %1\n\t"
+                     "v_dot2_u32_u16 %2, %[y], %[lo], %2\n\tv_dot2_u32_u16 %3, %[y], %[hi], %3\n\t"
+                     "v_dot2_u32_u16 %4, %[z], %[lo], %4\n\tv_dot2_u32_u16 %5, %[z], %[hi], %5\n\t"
+                     "v_dot2_u32_u16 %6, %[w], %[lo], %6\n\tv_dot2_u32_u16 %7, %[w], %[hi], %7"
+                     : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
+                     : [x] "v"(v.x), [y] "v"(v.y), [z] "v"(v.z), [w] "v"(v.w), [wn] "n"(WAITN), [lo] "v"(c_lo), [hi] "v"(c_hi));
     }
-#undef ADAPT_DRAIN_
-#undef ADAPT_SDOTS_
-#undef ADAPT_UDOTS_
-#undef ADAPT_ACC_
 }
 
 // row_fetch: activation = `bits`-wide field at bit SHIFT of word; read the 16 bytes of this lane's
 // column in that activation's line.  col = LDS address of the column in line 0 of table buffer 0 or 2,
-// OFF = 0 or 32768 selects the buffer after it.  COND: nothing is issued when on == 0.
-template <int SHIFT, int OFF, bool COND = false>
-__device__ __forceinline__ void row_fetch(u32x4_t &v, uint32_t word, uint32_t bits, uint32_t col, uint32_t on = 1) {
+// OFF = 0 or 32768 selects the buffer after it.
+template <int SHIFT, int OFF>
+__device__ __forceinline__ void row_fetch(u32x4_t &v, uint32_t word, uint32_t bits, uint32_t col) {
     uint32_t tmp;
-    if constexpr (COND)
-        asm volatile("s_cmp_eq_u32 %[on], 0\n\ts_cbranch_scc1 .Lrf_%=\n\t"
-                     "v_bfe_u32 %[t], %[wd], %[sh], %[bits]\n\t"
-                     "v_lshl_add_u32 %[t], %[t], 7, %[col]\n\t"
-                     "ds_read_b128 %[v], %[t] offset:%[off]\n"
-                     ".Lrf_%=:"
-                     : [v] "+v"(v), [t] "=&v"(tmp)
-                     : [wd] "v"(word), [sh] "n"(SHIFT), [bits] "s"(bits), [col] "v"(col), [off] "n"(OFF), [on] "s"(on)
-                     : "scc");
-    else
-        asm volatile("v_bfe_u32 %[t], %[wd], %[sh], %[bits]\n\t"
-                     "v_lshl_add_u32 %[t], %[t], 7, %[col]\n\t"
-                     "ds_read_b128 %[v], %[t] offset:%[off]"
-                     : [v] "+v"(v), [t] "=&v"(tmp)
-                     : [wd] "v"(word), [sh] "n"(SHIFT), [bits] "s"(bits), [col] "v"(col), [off] "n"(OFF));
+    asm volatile("v_bfe_u32 %[t], %[wd], %[sh], %[bits]\n\t"
+                 "v_lshl_add_u32 %[t], %[t], 7, %[col]\n\t"
+                 "ds_read_b128 %[v], %[t] offset:%[off]"
+                 : [v] "+v"(v), [t] "=&v"(tmp)
+                 : [wd] "v"(word), [sh] "n"(SHIFT), [bits] "s"(bits), [col] "v"(col), [off] "n"(OFF));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -721,28 +687,26 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     const uint32_t dma_voff = (uint32_t)(wave * lanes_act + lane) * 16u;
     const uint32_t lds_tbl = (uint32_t)(uintptr_t)(lds_void_ptr)tbl;
     const uint32_t lds_wave = lds_tbl + (uint32_t)(wave * lanes_act) * 16u;
-    // table `step` -> buffer `buf`, only if step < steps (decided inside the statement, see row_add)
-    auto dma = [&](int step, int buf) {
+    // table min(step, steps - 1) -> buffer `buf`.  Past the last table the copy is repeated into a buffer nobody reads any
+    // more, so that every group issues the same operations and the wait counts below hold to the end.
+    auto dma = [&](int step_, int buf) {
+        const int step = step_ < steps ? step_ : steps - 1;
         const unsigned char *src = dt + (size_t)(unsigned)step * table_bytes;
         const uint32_t m0v = lds_wave + (uint32_t)buf * (TABLE_U4_MAX * 16u);
         if constexpr (TWO_OPS) {
-            asm volatile("s_cmp_ge_i32 %[st], %[ns]\n\ts_cbranch_scc1 .Ldma_%=\n\t"
-                         "s_mov_b32 m0, %[ma]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[vo], %[sa]\n\t"
-                         "s_mov_b32 m0, %[mb]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[vo], %[sb]\n"
-                         ".Ldma_%=:"
+            asm volatile("s_mov_b32 m0, %[ma]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[vo], %[sa]\n\t"
+                         "s_mov_b32 m0, %[mb]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[vo], %[sb]"
                          :
-                         : [st] "s"(step), [ns] "s"(steps), [vo] "v"(dma_voff), [sa] "s"(src), [sb] "s"(src + 16384), [ma] "s"(m0v), [mb] "s"(m0v + 16384u)
-                         : "memory", "m0", "scc");
+                         : [vo] "v"(dma_voff), [sa] "s"(src), [sb] "s"(src + 16384), [ma] "s"(m0v), [mb] "s"(m0v + 16384u)
+                         : "memory", "m0");
         } else {
             uint64_t save;
-            asm volatile("s_cmp_ge_i32 %[st], %[ns]\n\ts_cbranch_scc1 .Ldma_%=\n\t"
-                         "s_mov_b64 %[sv], exec\n\ts_mov_b64 exec, %[mk]\n\t"
+            asm volatile("s_mov_b64 %[sv], exec\n\ts_mov_b64 exec, %[mk]\n\t"
                          "s_mov_b32 m0, %[ma]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[vo], %[sa]\n\t"
-                         "s_mov_b64 exec, %[sv]\n"
-                         ".Ldma_%=:"
+                         "s_mov_b64 exec, %[sv]"
                          : [sv] "=&s"(save)
-                         : [st] "s"(step), [ns] "s"(steps), [vo] "v"(dma_voff), [sa] "s"(src), [ma] "s"(m0v), [mk] "s"(dma_mask)
-                         : "memory", "m0", "scc");
+                         : [vo] "v"(dma_voff), [sa] "s"(src), [ma] "s"(m0v), [mk] "s"(dma_mask)
+                         : "memory", "m0");
         }
     };
 
@@ -750,17 +714,40 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     constexpr int NB = XMAJOR ? 2 : (REGULAR ? 1 : R);
     uint32_t base[NB];
     uint32_t row_step = 0;
+    // position of row r: image, output row a, output column b; the run after an x-major run of 4 pixels follows
+    // without further divisions (Wo and HoWo are multiples of 4 there)
+    auto row_pos = [&](int r, int &img, int &a, int &b) {
+        img = r / p.HoWo;
+        const int pix = r - img * p.HoWo;
+        a = pix / p.Wo;
+        b = pix - a * p.Wo;
+    };
+    auto next_run = [&](int &img, int &a, int &b) {
+        b += 4;
+        if (b == p.Wo) { b = 0; ++a; }
+        if (a * p.Wo == p.HoWo) { a = 0; ++img; }
+    };
     {
         int r0 = mt * (128 * R) + rs * R;
         if (REGULAR && r0 > p.M - R) r0 = p.M - R;
+        if constexpr (XMAJOR) {
+            int img, a, b;
+            row_pos(r0, img, a, b);
 #pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            int r = r0 + (XMAJOR ? 4 * i : i);
-            if (r >= p.M) r = p.M - 1;
-            const int img = r / p.HoWo, pix = r - img * p.HoWo;
-            const int oy = pix / p.Wo, ox = pix - oy * p.Wo;
-            base[i] = (uint32_t)((long long)img * p.img_stride + (long long)oy * p.oy_stride + (long long)ox * p.ox_stride +
-                                 (XMAJOR ? j * p.Cc * p.ch_stride : j * p.Cc));
+            for (int i = 0; i < 2; ++i) {
+                base[i] = (uint32_t)((long long)img * p.img_stride + (long long)a * p.oy_stride + (long long)b * p.ox_stride +
+                                     j * p.Cc * p.ch_stride);
+                next_run(img, a, b);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                int r = r0 + i;
+                if (r >= p.M) r = p.M - 1;
+                int img, a, b;
+                row_pos(r, img, a, b);
+                base[i] = (uint32_t)((long long)img * p.img_stride + (long long)a * p.oy_stride + (long long)b * p.ox_stride + j * p.Cc);
+            }
         }
         if (REGULAR) row_step = p.HoWo == 1 ? (uint32_t)p.img_stride : (uint32_t)p.ox_stride;
     }
@@ -771,35 +758,23 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
         uint32_t w[XMAJOR ? 1 : R];
         __device__ __forceinline__ uint32_t row(int i) const { return XMAJOR ? q[i / 4][i % 4] : w[i]; }
     };
-    auto load_acts = [&](Acts &a, uint32_t on, const int8_t *xrow) {
+    auto load_acts = [&](Acts &a, const int8_t *xrow) {
         if constexpr (XMAJOR) {     // 4 consecutive pixels x 4 channel bytes are 16 contiguous bytes
-            asm volatile("s_cmp_eq_u32 %[on], 0\n\ts_cbranch_scc1 .Lla_%=\n\t"
-                         "global_load_dwordx4 %[a0], %[b0], %[xr]\n\tglobal_load_dwordx4 %[a1], %[b1], %[xr]\n"
-                         ".Lla_%=:"
+            asm volatile("global_load_dwordx4 %[a0], %[b0], %[xr]\n\tglobal_load_dwordx4 %[a1], %[b1], %[xr]"
                          : [a0] "+v"(a.q[0]), [a1] "+v"(a.q[1])
-                         : [b0] "v"(base[0]), [b1] "v"(base[NB - 1]), [xr] "s"(xrow), [on] "s"(on)
-                         : "scc");
+                         : [b0] "v"(base[0]), [b1] "v"(base[NB - 1]), [xr] "s"(xrow));
         } else {
 #pragma unroll
             for (int i = 0; i < R; ++i) {
                 const int8_t *srow = REGULAR ? xrow + (size_t)i * row_step : xrow;
-                asm volatile("s_cmp_eq_u32 %[on], 0\n\ts_cbranch_scc1 .Lla_%=\n\t"
-                             "global_load_dword %[a0], %[b0], %[xr]\n"
-                             ".Lla_%=:"
-                             : [a0] "+v"(a.w[i])
-                             : [b0] "v"(base[REGULAR ? 0 : i]), [xr] "s"(srow), [on] "s"(on)
-                             : "scc");
+                asm volatile("global_load_dword %[a0], %[b0], %[xr]" : [a0] "+v"(a.w[i]) : [b0] "v"(base[REGULAR ? 0 : i]), [xr] "s"(srow));
             }
         }
     };
-    // end of a step: wait until at most IMM's count of this wave's memory operations are outstanding (all of them when
-    // at most one more group follows: the schedule of the last two groups is incomplete), then meet the other waves
-    auto step_end = [&](uint32_t rem, auto imm) {
-        asm volatile("s_cmp_gt_u32 %[dr], 1\n\ts_cbranch_scc1 .Lse_%=\n\ts_waitcnt vmcnt(0)\n.Lse_%=:\n\t"
-                     "s_waitcnt %[im]\n\ts_barrier"
-                     :
-                     : [dr] "s"(rem), [im] "n"(decltype(imm)::value)
-                     : "memory", "scc");
+    // end of a step: wait until at most the given number of this wave's memory operations are outstanding, then meet
+    // the other waves
+    auto step_end = [&](auto imm) {
+        asm volatile("s_waitcnt %[im]\n\ts_barrier" : : [im] "n"(decltype(imm)::value) : "memory");
     };
 
     uint32_t acc[R * 8];
@@ -840,8 +815,8 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     dma(0, 0);
     dma(1, 1);
     dma(2, 2);
-    load_acts(aw, 1u, xt);
-    step_end(0u, std::integral_constant<int, WAIT_ALL>{});
+    load_acts(aw, xt);
+    step_end(std::integral_constant<int, WAIT_ALL>{});
     advance_group();
     // first-half entries of step 0
 #pragma unroll
@@ -849,44 +824,47 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
 
     for (int g = 0; g < groups; ++g) {
         const int s0 = g << 2;
-        const uint32_t rem = (uint32_t)(groups - 1 - g);        // groups that follow this one
-        // u = 0: table buffers 0 (this step) and 1 (next step)
+        // u = 0: table buffers 0 (this step) and 1 (next step); activations of the next group (after the last group:
+        // those of the first one again, unused)
         dma(s0 + 3, 3);
-        load_acts(awn, rem, xt + tapoff + t4off);
+        load_acts(awn, g + 1 < groups ? xt + tapoff + t4off : xt);
 #pragma unroll
         for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<0, 0>(rv[i], aw.row(H + i), ubits, cb0); }
 #pragma unroll
         for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<8, 32768>(rv[i], aw.row(i), ubits, cb0); }
-        step_end(rem, std::integral_constant<int, WAIT_DA>{});
+        step_end(std::integral_constant<int, WAIT_DA>{});
         // u = 1: buffers 1 and 2
         dma(s0 + 4, 0);
 #pragma unroll
         for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<8, 32768>(rv[i], aw.row(H + i), ubits, cb0); }
 #pragma unroll
         for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<16, 0>(rv[i], aw.row(i), ubits, cb2); }
-        step_end(rem, std::integral_constant<int, WAIT_DA>{});
+        step_end(std::integral_constant<int, WAIT_DA>{});
         // u = 2: buffers 2 and 3
         dma(s0 + 5, 1);
 #pragma unroll
         for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<16, 0>(rv[i], aw.row(H + i), ubits, cb2); }
 #pragma unroll
         for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<24, 32768>(rv[i], aw.row(i), ubits, cb2); }
-        step_end(rem, std::integral_constant<int, WAIT_D>{});
+        step_end(std::integral_constant<int, WAIT_D>{});
         // u = 3: buffers 3 and 0; the second-half fetches are the first rows of the next group's first step (awn has
-        // landed: the wait that ended u = 2 covers it).  In the last group they are not issued, so every addition of
-        // that half waits for all outstanding reads.
+        // landed: the wait that ended u = 2 covers it; after the last group they read a stale table and are discarded)
         dma(s0 + 6, 2);
 #pragma unroll
         for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<24, 32768>(rv[i], aw.row(H + i), ubits, cb2); }
 #pragma unroll
-        for (int i = 0; i < H; ++i) {
-            row_add<SIGNED, WN, true>(acc + (H + i) * 8, rv[i], rem);
-            row_fetch<0, 0, true>(rv[i], awn.row(i), ubits, cb0, rem);
-        }
-        step_end(rem, std::integral_constant<int, WAIT_D>{});
+        for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<0, 0>(rv[i], awn.row(i), ubits, cb0); }
+        step_end(std::integral_constant<int, WAIT_D>{});
         aw = awn;
         advance_group();
     }
+    // retire the reads and copies issued past the end before the compiler may reuse their registers
+    if constexpr (H == 4)
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" : "+v"(rv[0]), "+v"(rv[1]), "+v"(rv[2]), "+v"(rv[3]) : : "memory");
+    else if constexpr (H == 2)
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" : "+v"(rv[0]), "+v"(rv[1]) : : "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" : "+v"(rv[0]) : : "memory");
 
     // reduce the partial sums of the 8 k-subs (lanes j = 0..7 of a row slot) with lane permutes inside
     // the vector ALU: swap within pairs, within quads, then mirror the 8-lane half row
@@ -913,12 +891,11 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
                 for (int c = 1; c < 8; ++c) v[i] = (j == c) ? acc[i * 8 + c] : v[i];
                 if (p.shift < 0) v[i] = finish_sum(p, v[i], n);
             }
+            int img, a0, b0;
+            row_pos(r0 < p.M ? r0 : 0, img, a0, b0);
 #pragma unroll
             for (int hq = 0; hq < 2; ++hq) {
-                const int r = r0 + 4 * hq;
-                if (r + 4 <= p.M) {
-                    const int img = r / p.HoWo, pix = r - img * p.HoWo;
-                    const int a0 = pix / p.Wo, b0 = pix - a0 * p.Wo;
+                if (r0 + 8 <= p.M) {        // M is a multiple of 8 here
                     int32_t *q0 = p.out + ((size_t)img * p.N + n) * p.out_plane + out_off + a0 * p.out_sy + b0 * p.out_sx;
                     if (p.shift < 0 && p.out_sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
                         *reinterpret_cast<uint4 *>(q0) = make_uint4(v[4 * hq], v[4 * hq + 1], v[4 * hq + 2], v[4 * hq + 3]);
@@ -931,6 +908,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
                         }
                     }
                 }
+                next_run(img, a0, b0);
             }
         } else {
 #pragma unroll
