@@ -434,6 +434,9 @@ struct LinesCall {       // per-call geometry of the activation side
     int xmajor, ch_stride;  // x-major activation copy (see pad_channels_last_kernel) and its bytes per channel step
     int out_plane, out_sy, out_sx;      // see adapt::LinesParams
     std::vector<LinesPhase> phases;
+    int32_t *partial = nullptr;         // room for the partial sums when the plan splits the inner dimension
+    size_t out_elems = 0;               // elements of the whole output tensor
+    size_t out_channels = 1, out_inner = 1;     // where the channel sits in a flat output index: (i / inner) % channels
 };
 
 int device_cus() {
@@ -442,20 +445,51 @@ int device_cus() {
     return cu;
 }
 
-// rows per lane: as many as still give every compute unit a workgroup
-int lines_rows_per_lane(int M, int n_tiles) {
+// How a product is spread over the chip.  Rows per lane R (a workgroup handles 128 R rows): as many as still give every
+// compute unit a workgroup, because table traffic per multiply-accumulate falls with R.  When even the largest tile
+// leaves compute units idle and the inner dimension is long enough, keep R = 8 and split the inner dimension over
+// `ksplit` workgroups instead (each streams only its slice of the tables; a small kernel adds the partial sums).
+struct LinesPlan {
+    int R, ksplit, gps;      // gps: groups of four steps per slice
+};
+
+LinesPlan lines_plan(int M, int tiles, int Cc, int taps) {
     const int cu = device_cus();
-    int R = 8;
-    while (R > 2 && (long long)((M + 128 * R - 1) / (128 * R)) * n_tiles < cu) R /= 2;
-    return R;
+    auto wgs = [&](int r) { return (long long)((M + 128 * r - 1) / (128 * r)) * tiles; };
+    LinesPlan pl{8, 1, 0};
+    const int groups = Cc % 4 == 0 ? taps * Cc / 4 : 0;        // the split needs the fast kernel
+    if (wgs(8) < cu && groups >= 8) {
+        int ks = (int)(cu / wgs(8));
+        if (ks > groups / 4) ks = groups / 4;                   // at least four groups (16 steps) per slice
+        if (ks > 16) ks = 16;
+        if (ks >= 2) {
+            pl.gps = (groups + ks - 1) / ks;
+            pl.ksplit = (groups + pl.gps - 1) / pl.gps;
+            return pl;
+        }
+    }
+    while (pl.R > 2 && wgs(pl.R) < cu) pl.R /= 2;
+    pl.gps = groups > 0 ? groups : 1;
+    return pl;
+}
+
+int lines_rows_per_lane(int M, int tiles, int Cc, int taps) { return lines_plan(M, tiles, Cc, taps).R; }
+
+// bytes of partial sums a call needs (0 without a split of the inner dimension)
+size_t lines_partial_bytes(int M, int tiles, int Cc, int taps, size_t out_elems) {
+    const LinesPlan pl = lines_plan(M, tiles, Cc, taps);
+    return pl.ksplit > 1 ? (size_t)pl.ksplit * out_elems * sizeof(int32_t) : 0;
 }
 
 int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *xt, const LinesCall &c,
               int32_t *out, hipStream_t s, const LayerIO *io = nullptr, bool may_fuse = true) {
     const int n_phases = (int)c.phases.size();
-    const int R = lines_rows_per_lane(c.M, q.n_tiles * n_phases);
+    const LinesPlan pl = lines_plan(c.M, q.n_tiles * n_phases, q.Cc, q.kh * q.kw);
+    const int R = pl.R;
+    const bool split = pl.ksplit > 1;
+    if (split && !c.partial) return fail(ADAPT_ERR_HIP, "lines path: no room for partial sums");
     adapt::LinesParams p;
-    p.xt = xt; p.out = out;
+    p.xt = xt;
     p.M = c.M; p.N = q.N; p.n_tiles = q.n_tiles;
     p.Cc = q.Cc; p.taps = q.kh * q.kw; p.kw = q.kw; p.bits = bits;
     p.HoWo = c.HoWo; p.Wo = c.Wo; p.img_stride = c.img_stride;
@@ -463,29 +497,40 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     p.ch_stride = c.ch_stride;
     p.out_plane = c.out_plane; p.out_sy = c.out_sy; p.out_sx = c.out_sx;
     p.m_tiles = (c.M + 128 * R - 1) / (128 * R);
+    p.ksplit = pl.ksplit; p.gps = pl.gps; p.ks_out_stride = split ? (long long)c.out_elems : 0;
     const bool fuse = may_fuse && io && io->fused(storage);
-    p.deq = fuse ? 1 : 0; p.act = fuse ? io->act : 0; p.scale = fuse ? io->s_out : 1.0f; p.bias = fuse ? io->bias : nullptr;
+    const bool fuse_in_kernel = fuse && !split;
+    p.deq = fuse_in_kernel ? 1 : 0; p.act = fuse_in_kernel ? io->act : 0;
+    p.scale = fuse_in_kernel ? io->s_out : 1.0f; p.bias = fuse_in_kernel ? io->bias : nullptr;
     // one base offset per lane is enough when the R rows of a lane are equally spaced in xt
     const bool regular = (c.M % R == 0) && (c.HoWo == 1 || c.Wo % R == 0);
     const bool xmajor = c.xmajor && R == 8 && c.M % 8 == 0 && c.Wo % 4 == 0;
     if (c.xmajor && !xmajor) return fail(ADAPT_ERR_HIP, "lines path: x-major copy without 8 rows per lane in runs of 4 pixels");
     int rc = ADAPT_OK;
-    for (int first = 0; first < n_phases && rc == ADAPT_OK; first += 4) {       // up to four phases per launch
-        p.phases = n_phases - first < 4 ? n_phases - first : 4;
-        for (int i = 0; i < 4; ++i) {
-            const LinesPhase &f = c.phases[first + (i < p.phases ? i : 0)];
-            p.xt_off[i] = f.xt_off; p.out_off[i] = f.out_off; p.dt_off[i] = f.dt_off;
-        }
-        const long long grid = (long long)p.m_tiles * q.n_tiles * p.phases;
-        if (grid > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "lines path: grid too large");
-        for (int half = 0; half <= storage && rc == ADAPT_OK; ++half) {
-            p.dt = dt[half];
-            p.shift = half == 0 ? -1 : 16;
-            const bool sgn = storage == 0 || half == 1;
+    for (int half = 0; half <= storage && rc == ADAPT_OK; ++half) {
+        p.dt = dt[half];
+        p.out = split ? c.partial : out;
+        p.shift = (half == 0 || split) ? -1 : 16;
+        const bool sgn = storage == 0 || half == 1;
+        for (int first = 0; first < n_phases && rc == ADAPT_OK; first += 4) {       // up to four phases per launch
+            p.phases = n_phases - first < 4 ? n_phases - first : 4;
+            for (int i = 0; i < 4; ++i) {
+                const LinesPhase &f = c.phases[first + (i < p.phases ? i : 0)];
+                p.xt_off[i] = f.xt_off; p.out_off[i] = f.out_off; p.dt_off[i] = f.dt_off;
+            }
+            const long long grid = (long long)p.m_tiles * q.n_tiles * p.phases * p.ksplit;
+            if (grid > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "lines path: grid too large");
             if (xmajor) rc = sgn ? launch_lines_xmajor<true>(p, (unsigned)grid, s) : launch_lines_xmajor<false>(p, (unsigned)grid, s);
             else if (R == 8) rc = launch_lines_r<8>(p, (unsigned)grid, sgn, regular, s);
             else if (R == 4) rc = launch_lines_r<4>(p, (unsigned)grid, sgn, regular, s);
             else rc = launch_lines_r<2>(p, (unsigned)grid, sgn, regular, s);
+        }
+        if (split && rc == ADAPT_OK) {
+            adapt::reduce_partials_kernel<<<ew_grid(c.out_elems), adapt::EW_THREADS, 0, s>>>(
+                c.partial, pl.ksplit, c.out_elems, out, c.out_elems, half == 0 ? -1 : 16, (fuse && half == 0) ? 1 : 0, c.out_channels,
+                c.out_inner, fuse ? io->s_out : 1.0f, fuse ? io->bias : nullptr, fuse ? io->act : 0);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) rc = fail(ADAPT_ERR_HIP, "reduce_partials launch: %s", hipGetErrorString(e));
         }
     }
     return rc;
@@ -503,10 +548,13 @@ int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     LinesCall c;
     c.M = M;
     c.phases.resize(1);
-    if (lines_rows_per_lane(M, q.n_tiles) == 8 && M % 8 == 0) {
+    c.out_elems = (size_t)M * q.N; c.out_channels = (size_t)q.N; c.out_inner = 1;
+    const size_t part_bytes = lines_partial_bytes(M, q.n_tiles, q.Cc, 1, c.out_elems);
+    const size_t copy_bytes = (((size_t)M * Kp + 64 + 255) / 256) * 256;
+    if (lines_rows_per_lane(M, q.n_tiles, q.Cc, 1) == 8 && M % 8 == 0) {
         // x-major copy: one image of one row of M pixels with K channels; a lane's 8 rows x 4 inner indices are 32
         // contiguous bytes instead of 8 words that are a whole matrix row apart
-        int wrc = ws_get(ws, (size_t)M * Kp + 64, s, (void **)&tmp);
+        int wrc = ws_get(ws, copy_bytes + part_bytes, s, (void **)&tmp);
         if (wrc) return wrc;
         dim3 grid((unsigned)((M + 63) / 64), (unsigned)((Kp / 4 + 15) / 16));
         if (from_f32) adapt::rows_to_xmajor_kernel<<<grid, 256, 0, s>>>(srcf, tmp, M, K, Kp);
@@ -517,9 +565,11 @@ int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
         c.xmajor = 1; c.ch_stride = M;
         c.out_plane = 1; c.out_sy = 0; c.out_sx = q.N;
     } else {
-        if (Kp != K || from_f32) {
-            int wrc = ws_get(ws, (size_t)M * Kp + 16, s, (void **)&tmp);
+        if (Kp != K || from_f32 || part_bytes) {
+            int wrc = ws_get(ws, copy_bytes + part_bytes, s, (void **)&tmp);
             if (wrc) return wrc;
+        }
+        if (Kp != K || from_f32) {
             const size_t total = (size_t)M * Kp;
             size_t blocks = (total + 255) / 256;
             if (blocks > 65536) blocks = 65536;
@@ -532,6 +582,7 @@ int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
         c.xmajor = 0; c.ch_stride = 0;
         c.out_plane = 1; c.out_sy = 0; c.out_sx = 0;
     }
+    if (part_bytes) c.partial = reinterpret_cast<int32_t *>(tmp + copy_bytes);
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io);
     rc = ws_put(ws, tmp, s, rc);
     if (rc == ADAPT_OK && io && io->deq && !io->fused(storage)) rc = finish_inplace(out, (size_t)M * q.N, (size_t)q.N, 1, *io, s);
@@ -547,10 +598,14 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     // With 8 rows per lane that are 8 consecutive output pixels of a stride-1 convolution, the copy is laid
     // out so that these rows' activations are contiguous (one wide load per lane instead of one per row).
     const int M = N * Ho * Wo;
-    const int xmajor = (lines_rows_per_lane(M, q.n_tiles) == 8 && Wo % 4 == 0 && M % 8 == 0 && sw == 1 && q.Cc % 4 == 0) ? 1 : 0;
+    const int taps = q.kh * q.kw;
+    const int xmajor = (lines_rows_per_lane(M, q.n_tiles, q.Cc, taps) == 8 && Wo % 4 == 0 && M % 8 == 0 && sw == 1 && q.Cc % 4 == 0) ? 1 : 0;
+    const size_t out_elems = (size_t)M * q.N;
+    const size_t part_bytes = lines_partial_bytes(M, q.n_tiles, q.Cc, taps, out_elems);
+    const size_t copy_bytes = ((xt_bytes + 64 + 255) / 256) * 256;
     int8_t *xt = nullptr;
     {
-        int wrc = ws_get(ws, xt_bytes + 64, s, (void **)&xt);
+        int wrc = ws_get(ws, copy_bytes + part_bytes, s, (void **)&xt);
         if (wrc) return wrc;
         const size_t total = xt_bytes / 4;
         size_t blocks = (total + 255) / 256;
@@ -569,6 +624,8 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     c.xmajor = xmajor; c.ch_stride = Wp;
     c.out_plane = Ho * Wo; c.out_sy = Wo; c.out_sx = 1;
     c.phases.resize(1);
+    c.out_elems = out_elems; c.out_channels = (size_t)q.N; c.out_inner = (size_t)Ho * Wo;
+    if (part_bytes) c.partial = reinterpret_cast<int32_t *>(xt + copy_bytes);
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io);
     rc = ws_put(ws, xt, s, rc);
     if (rc == ADAPT_OK && io && io->deq && !io->fused(storage))
@@ -595,10 +652,13 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
     const int Qy = Ho / st, Qx = Wo / st;
     const int M = N * Qy * Qx;
     const size_t xt_bytes = (size_t)N * Hp * Wp * Cp;
-    const int xmajor = (lines_rows_per_lane(M, q.n_tiles * st * st) == 8 && Qx % 4 == 0 && M % 8 == 0 && q.Cc % 4 == 0) ? 1 : 0;
+    const int xmajor = (lines_rows_per_lane(M, q.n_tiles * st * st, q.Cc, Ty * Tx) == 8 && Qx % 4 == 0 && M % 8 == 0 && q.Cc % 4 == 0) ? 1 : 0;
+    const size_t out_elems = (size_t)N * q.N * Ho * Wo;
+    const size_t part_bytes = lines_partial_bytes(M, q.n_tiles * st * st, q.Cc, Ty * Tx, out_elems);
+    const size_t copy_bytes = ((xt_bytes + 64 + 255) / 256) * 256;
     int8_t *xt = nullptr;
     {
-        int wrc = ws_get(ws, xt_bytes + 64, s, (void **)&xt);
+        int wrc = ws_get(ws, copy_bytes + part_bytes, s, (void **)&xt);
         if (wrc) return wrc;
         const size_t total = xt_bytes / 4;
         size_t blocks = (total + 255) / 256;
@@ -630,6 +690,8 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
     // window taps over the zero border were looked up; the layer is defined over real pairs only
     const int Ly = kh - st - pad > 0 ? kh - st - pad : 0, Lx = kw - st - pad > 0 ? kw - st - pad : 0;
     const bool border = Ly > 0 || Lx > 0;       // then the sums are corrected before they can be rescaled
+    c.out_elems = out_elems; c.out_channels = (size_t)q.N; c.out_inner = (size_t)Ho * Wo;
+    if (part_bytes) c.partial = reinterpret_cast<int32_t *>(xt + copy_bytes);
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io, !border);
     rc = ws_put(ws, xt, s, rc);
     if (rc != ADAPT_OK) return rc;

@@ -67,6 +67,11 @@ struct LinesParams {
     int xt_off[4];          // bytes into xt
     int out_off[4];         // elements into an output plane
     long long dt_off[4];    // 16-byte units into dt
+    // Split of the inner dimension over workgroups (fast kernel only): workgroup slice ks handles the groups of four
+    // steps [ks * gps, min(groups, (ks + 1) * gps)) and stores its partial sums at out + ks * ks_out_stride (elements);
+    // reduce_partials_kernel adds the slices up.  ksplit == 1: no split.
+    int ksplit, gps;
+    long long ks_out_stride;
 };
 
 // what is stored for the finished sum v of output channel n (see LinesParams::deq)
@@ -324,6 +329,30 @@ __global__ __launch_bounds__(EW_THREADS) void finish_inplace_kernel(int32_t *__r
         if (act == 1) y = y > 0.0f ? y : 0.0f;
         else if (act == 2) y = tanh_spec(y);
         reinterpret_cast<float *>(buf)[i] = y;
+    }
+}
+
+// out[i] = sum over the ks slices of part[k * stride + i]; then either stored (shift < 0; deq != 0: rescaled as in
+// finish_inplace_kernel) or added to out[i] after a left shift (second half of a two-pass table)
+__global__ __launch_bounds__(EW_THREADS) void reduce_partials_kernel(const int32_t *__restrict__ part, int ks, size_t stride_elems,
+                                                                     int32_t *__restrict__ out, size_t n, int shift, int deq,
+                                                                     size_t channels, size_t inner, float scale,
+                                                                     const float *__restrict__ bias, int act) {
+    const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
+        uint32_t v = 0;
+        for (int k = 0; k < ks; ++k) v += (uint32_t)part[(size_t)k * stride_elems + i];
+        if (shift >= 0) {
+            out[i] = (int32_t)((uint32_t)out[i] + (v << shift));
+        } else if (deq) {
+            float y = (float)(int32_t)v * scale;
+            if (bias) y = y + bias[(i / inner) % channels];
+            if (act == 1) y = y > 0.0f ? y : 0.0f;
+            else if (act == 2) y = tanh_spec(y);
+            reinterpret_cast<float *>(out)[i] = y;
+        } else {
+            out[i] = (int32_t)v;
+        }
     }
 }
 
@@ -670,20 +699,26 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     const int nt = blockIdx.x % p.n_tiles;
     const int wg = blockIdx.x / p.n_tiles;
     const int mt = wg % p.m_tiles;
-    const int ph = wg / p.m_tiles;
+    const int pk = wg / p.m_tiles;
+    const int ph = pk % p.phases;
+    const int ks = pk / p.phases;               // slice of the inner dimension
     const int8_t *const xt = p.xt + pick4(p.xt_off, ph);
     const int out_off = pick4(p.out_off, ph);
+    int32_t *const outp = p.out + (size_t)ks * p.ks_out_stride;
     const int lines = 1 << p.bits;
     const int table_u4 = lines * 8;
-    const int steps = p.taps * p.Cc;
-    const int groups = steps >> 2;
-    const unsigned char *dt = reinterpret_cast<const unsigned char *>(p.dt + pick4(p.dt_off, ph) + (size_t)nt * steps * table_u4);
+    const int steps_all = p.taps * p.Cc;
+    const int g_begin = ks * p.gps;
+    const int groups = min(steps_all >> 2, g_begin + p.gps) - g_begin;      // groups of this slice (>= 1)
+    const int steps = groups << 2;
     const uint32_t table_bytes = (uint32_t)table_u4 * 16u;
+    const unsigned char *dt = reinterpret_cast<const unsigned char *>(p.dt + pick4(p.dt_off, ph) + (size_t)nt * steps_all * table_u4) +
+                              (size_t)(g_begin << 2) * table_bytes;
 
     // table copy geometry: 8-bit tables take two operations of 64 lanes per wave, smaller tables one
     // operation of table_u4 / 16 lanes per wave
     const int lanes_act = TWO_OPS ? 64 : (table_u4 >> 4);
-    const uint64_t dma_mask = lanes_act >= 64 ? ~0ull : ((1ull << lanes_act) - 1ull);
+    const uint64_t dma_mask = ~0ull >> (64 - lanes_act);       // 1 <= lanes_act <= 64
     const uint32_t dma_voff = (uint32_t)(wave * lanes_act + lane) * 16u;
     const uint32_t lds_tbl = (uint32_t)(uintptr_t)(lds_void_ptr)tbl;
     const uint32_t lds_wave = lds_tbl + (uint32_t)(wave * lanes_act) * 16u;
@@ -781,9 +816,13 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
 #pragma unroll
     for (int q = 0; q < R * 8; ++q) acc[q] = 0;
 
-    // position of the NEXT group's activations
-    int kx = 0, t4 = 0, t4off = 0;             // t4off: byte offset of inner index t4 within a tap
-    uint32_t tapoff = 0, rowoff = 0;           // kx * kx_stride + ky * ky_stride, split so both advance by additions
+    // position of the NEXT group's activations (starts at this slice's first group)
+    const int tap0 = (g_begin << 2) / p.Cc;
+    const int ky0 = tap0 / p.kw;
+    int kx = tap0 - ky0 * p.kw, t4 = (g_begin << 2) - tap0 * p.Cc;
+    int t4off = XMAJOR ? t4 * p.ch_stride : t4;                 // byte offset of inner index t4 within a tap
+    uint32_t rowoff = (uint32_t)(ky0 * p.ky_stride);            // ky * ky_stride
+    uint32_t tapoff = rowoff + (uint32_t)(kx * p.kx_stride);    // + kx * kx_stride; both advance by additions
     auto advance_group = [&]() {
         t4 += 4;
         t4off += XMAJOR ? 4 * p.ch_stride : 4;
@@ -815,7 +854,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     dma(0, 0);
     dma(1, 1);
     dma(2, 2);
-    load_acts(aw, xt);
+    load_acts(aw, xt + tapoff + t4off);
     step_end(std::integral_constant<int, WAIT_ALL>{});
     advance_group();
     // first-half entries of step 0
@@ -896,7 +935,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
 #pragma unroll
             for (int hq = 0; hq < 2; ++hq) {
                 if (r0 + 8 <= p.M) {        // M is a multiple of 8 here
-                    int32_t *q0 = p.out + ((size_t)img * p.N + n) * p.out_plane + out_off + a0 * p.out_sy + b0 * p.out_sx;
+                    int32_t *q0 = outp + ((size_t)img * p.N + n) * p.out_plane + out_off + a0 * p.out_sy + b0 * p.out_sx;
                     if (p.shift < 0 && p.out_sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
                         *reinterpret_cast<uint4 *>(q0) = make_uint4(v[4 * hq], v[4 * hq + 1], v[4 * hq + 2], v[4 * hq + 3]);
                     } else {
@@ -922,7 +961,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
                     if (REGULAR && p.HoWo > 1) { img = img0; pix = pix0 + i; }      // R consecutive pixels of one output row
                     else { img = r / p.HoWo; pix = r - img * p.HoWo; }
                     const int a = pix / p.Wo, b = pix - a * p.Wo;
-                    int32_t *q = p.out + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
+                    int32_t *q = outp + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
                     if (p.shift < 0) *q = (int32_t)finish_sum(p, v, n);
                     else *q = (int32_t)((uint32_t)*q + (v << p.shift));
                 }

@@ -421,6 +421,7 @@ LINES_LINEAR = [
     (8192, 40, 256), (8197, 40, 256),        # 8 rows per lane
     (4096, 33, 256), (4099, 64, 250),        # 4 rows per lane
     (4096, 32, 16), (4101, 100, 9),          # 2 rows per lane
+    (4096, 512, 16), (4101, 300, 9), (8192, 256, 64),      # long inner dimension, few tiles: split over workgroups
 ]
 
 
@@ -628,6 +629,8 @@ def test_linear_layer_f32(B, kind, shape):
 
 LAYER_CONV = [
     # N, Cin, H, W, Cout, k, stride, pad
+    (16, 64, 8, 8, 64, 3, 1, 1),       # few tiles, long inner dimension: split over workgroups
+    (70, 32, 8, 8, 32, 3, 2, 1),
     (2, 3, 8, 8, 4, 3, 1, 1),
     (3, 16, 32, 32, 16, 3, 1, 1),
     (2, 16, 32, 32, 32, 3, 2, 1),
