@@ -109,6 +109,7 @@ struct adapt_weights {
     int bits, storage, device;
     int N, Cin, kh, kw;     // linear: Cin = K, kh = kw = 1
     int Cp, Cc, n_tiles;    // padded inner length (multiple of 8; linear: of 32), steps per tap, 8-channel tiles
+    int pair_g;             // taps per group of four steps when taps are paired (see adapt::LinesParams), else 0
     size_t dt_bytes;        // per table-half (transposed convolution: all phases together)
     uint4 *dt_dev[2];
     // transposed convolution only
@@ -367,6 +368,14 @@ int launch_lines_inst(const adapt::LinesParams &p, unsigned grid, hipStream_t s)
 
 template <int R, bool SIGNED, bool REGULAR>
 int launch_lines_fast(const adapt::LinesParams &p, unsigned grid, hipStream_t s) {
+    if constexpr (SIGNED) {
+        if (p.pair_g) {     // tap pairing exists for single-pass (signed) tables only
+            if (p.bits == 8) adapt::lut_lines_fast_kernel<R, true, REGULAR, true, false, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+            else adapt::lut_lines_fast_kernel<R, true, REGULAR, false, false, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+            HIP_TRY(hipGetLastError());
+            return ADAPT_OK;
+        }
+    }
     if (p.bits == 8) adapt::lut_lines_fast_kernel<R, SIGNED, REGULAR, true, false><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
     else adapt::lut_lines_fast_kernel<R, SIGNED, REGULAR, false, false><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
     HIP_TRY(hipGetLastError());
@@ -376,6 +385,14 @@ int launch_lines_fast(const adapt::LinesParams &p, unsigned grid, hipStream_t s)
 // x-major activation copy: 8 regular rows per lane
 template <bool SIGNED>
 int launch_lines_xmajor(const adapt::LinesParams &p, unsigned grid, hipStream_t s) {
+    if constexpr (SIGNED) {
+        if (p.pair_g) {
+            if (p.bits == 8) adapt::lut_lines_fast_kernel<8, true, true, true, true, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+            else adapt::lut_lines_fast_kernel<8, true, true, false, true, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+            HIP_TRY(hipGetLastError());
+            return ADAPT_OK;
+        }
+    }
     if (p.bits == 8) adapt::lut_lines_fast_kernel<8, SIGNED, true, true, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
     else adapt::lut_lines_fast_kernel<8, SIGNED, true, false, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
     HIP_TRY(hipGetLastError());
@@ -396,16 +413,23 @@ struct LinesShape {
     int kind;            // 0 linear, 1 conv2d
     int N, Cin, kh, kw;  // output channels, inner length per tap, taps
     int Cp, Cc, n_tiles;
+    int pair_g;          // > 0: tap pairing, that many taps per group of four steps (see adapt::LinesParams)
     size_t dt_bytes;     // per table half
+    // as the kernels see the inner dimension: steps per "tap" and number of "taps"
+    int k_cc() const { return pair_g ? 4 : Cc; }
+    int k_taps() const { return pair_g ? (kh * kw + pair_g - 1) / pair_g : kh * kw; }
 };
 
-LinesShape lines_shape(int kind, int bits, int N, int Cin, int kh, int kw) {
+// pairing: convolutions with 8 or 16 (padded) channels and a single-pass table pack 4 or 2 taps into a group of steps,
+// which lets them run on the fast kernel
+LinesShape lines_shape(int kind, int bits, int N, int Cin, int kh, int kw, bool may_pair = false) {
     LinesShape q;
     q.kind = kind; q.N = N; q.Cin = Cin; q.kh = kh; q.kw = kw;
     q.Cp = kind == 0 ? ((Cin + 31) / 32) * 32 : ((Cin + 7) / 8) * 8;
     q.Cc = q.Cp / 8;
     q.n_tiles = (N + 7) / 8;
-    q.dt_bytes = (size_t)q.n_tiles * kh * kw * q.Cc * ((size_t)adapt::LINE_BYTES << bits);
+    q.pair_g = (may_pair && kind == 1 && q.Cp <= 16) ? 32 / q.Cp : 0;
+    q.dt_bytes = (size_t)q.n_tiles * q.k_taps() * q.k_cc() * ((size_t)adapt::LINE_BYTES << bits);
     return q;
 }
 
@@ -415,7 +439,7 @@ int pack_lines(const adapt_lut *lut, const int8_t *w, const LinesShape &q, uint4
         size_t blocks = (total + 255) / 256;
         if (blocks > 65536) blocks = 65536;
         adapt::pack_line_tables_kernel<<<(unsigned)blocks, 256, 0, s>>>(lut->lut16_dev[half], w, dt[half], lut->bits, q.N, q.Cin,
-                                                                       q.kh * q.kw, q.Cc, q.n_tiles, 0);
+                                                                       q.kh * q.kw, q.Cc, q.n_tiles, 0, q.pair_g, q.Cp / 4);
         HIP_TRY(hipGetLastError());
     }
     return ADAPT_OK;
@@ -458,7 +482,7 @@ LinesPlan lines_plan(int M, int tiles, int Cc, int taps) {
     auto wgs = [&](int r) { return (long long)((M + 128 * r - 1) / (128 * r)) * tiles; };
     LinesPlan pl{8, 1, 0};
     const int groups = Cc % 4 == 0 ? taps * Cc / 4 : 0;        // the split needs the fast kernel
-    if (wgs(8) < cu && groups >= 8) {
+    if (wgs(8) * 4 <= cu && groups >= 8) {      // (with half the chip covered, 4 rows per lane does as well)
         int ks = (int)(cu / wgs(8));
         if (ks > groups / 4) ks = groups / 4;                   // at least four groups (16 steps) per slice
         if (ks > 16) ks = 16;
@@ -484,14 +508,16 @@ size_t lines_partial_bytes(int M, int tiles, int Cc, int taps, size_t out_elems)
 int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *xt, const LinesCall &c,
               int32_t *out, hipStream_t s, const LayerIO *io = nullptr, bool may_fuse = true) {
     const int n_phases = (int)c.phases.size();
-    const LinesPlan pl = lines_plan(c.M, q.n_tiles * n_phases, q.Cc, q.kh * q.kw);
+    const LinesPlan pl = lines_plan(c.M, q.n_tiles * n_phases, q.k_cc(), q.k_taps());
     const int R = pl.R;
     const bool split = pl.ksplit > 1;
     if (split && !c.partial) return fail(ADAPT_ERR_HIP, "lines path: no room for partial sums");
     adapt::LinesParams p;
     p.xt = xt;
     p.M = c.M; p.N = q.N; p.n_tiles = q.n_tiles;
-    p.Cc = q.Cc; p.taps = q.kh * q.kw; p.kw = q.kw; p.bits = bits;
+    p.Cc = q.k_cc(); p.taps = q.k_taps(); p.kw = q.kw; p.bits = bits;
+    p.pair_g = q.pair_g; p.pair_cg = q.Cp / 4; p.taps_real = q.kh * q.kw;
+    if (q.pair_g && storage != 0) return fail(ADAPT_ERR_HIP, "lines path: tap pairing with a two-pass table");
     p.HoWo = c.HoWo; p.Wo = c.Wo; p.img_stride = c.img_stride;
     p.oy_stride = c.oy_stride; p.ox_stride = c.ox_stride; p.ky_stride = c.ky_stride; p.kx_stride = c.kx_stride;
     p.ch_stride = c.ch_stride;
@@ -598,10 +624,10 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     // With 8 rows per lane that are 8 consecutive output pixels of a stride-1 convolution, the copy is laid
     // out so that these rows' activations are contiguous (one wide load per lane instead of one per row).
     const int M = N * Ho * Wo;
-    const int taps = q.kh * q.kw;
-    const int xmajor = (lines_rows_per_lane(M, q.n_tiles, q.Cc, taps) == 8 && Wo % 4 == 0 && M % 8 == 0 && sw == 1 && q.Cc % 4 == 0) ? 1 : 0;
+    const int xmajor = (lines_rows_per_lane(M, q.n_tiles, q.k_cc(), q.k_taps()) == 8 && Wo % 4 == 0 && M % 8 == 0 && sw == 1 &&
+                        q.k_cc() % 4 == 0) ? 1 : 0;
     const size_t out_elems = (size_t)M * q.N;
-    const size_t part_bytes = lines_partial_bytes(M, q.n_tiles, q.Cc, taps, out_elems);
+    const size_t part_bytes = lines_partial_bytes(M, q.n_tiles, q.k_cc(), q.k_taps(), out_elems);
     const size_t copy_bytes = ((xt_bytes + 64 + 255) / 256) * 256;
     int8_t *xt = nullptr;
     {
@@ -870,7 +896,7 @@ int adapt_approx_conv2d(const adapt_lut *lut, const int8_t *x_dev, const int8_t 
     g.sh = stride_h; g.sw = stride_w; g.ph = pad_h; g.pw = pad_w; g.dh = dil_h; g.dw = dil_w;
     g.kstride = H * W; g.img_stride = Cin * H * W;
     if (g.M >= LINES_MIN_ROWS && Cin >= 4) {
-        const LinesShape q = lines_shape(1, lut->bits, Cout, Cin, kh, kw);
+        const LinesShape q = lines_shape(1, lut->bits, Cout, Cin, kh, kw, lut->storage == 0);
         const long long xt_bytes = (long long)N * (H + 2LL * pad_h) * (W + 2LL * pad_w) * q.Cp;
         if (lines_fits(xt_bytes, q.dt_bytes, lut->storage))
             return with_temp_tables(lut, w_dev, q, (hipStream_t)stream, [&](uint4 *const dt[2]) {
@@ -910,13 +936,13 @@ static int weights_pack(adapt_weights **out, const adapt_lut *lut, const int8_t 
     if (N < 1 || Cin < 1 || kh < 1 || kw < 1) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
     if (!w_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: w_dev is NULL", who);
     if ((long long)N * Cin * kh * kw > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "%s: more than 2^31-1 weights", who);
-    const LinesShape q = lines_shape(kind, lut->bits, N, Cin, kh, kw);
+    const LinesShape q = lines_shape(kind, lut->bits, N, Cin, kh, kw, lut->storage == 0);
     if (q.dt_bytes * (size_t)(lut->storage + 1) > ((size_t)64 << 30))
         return fail(ADAPT_ERR_OUT_OF_MEMORY, "%s: packed tables would need %zu bytes", who, q.dt_bytes * (size_t)(lut->storage + 1));
     adapt_weights *h = new (std::nothrow) adapt_weights();
     if (!h) return fail(ADAPT_ERR_OUT_OF_MEMORY, "%s: host allocation failed", who);
     h->kind = kind; h->bits = lut->bits; h->storage = lut->storage; h->device = lut->device;
-    h->N = N; h->Cin = Cin; h->kh = kh; h->kw = kw; h->Cp = q.Cp; h->Cc = q.Cc; h->n_tiles = q.n_tiles;
+    h->N = N; h->Cin = Cin; h->kh = kh; h->kw = kw; h->Cp = q.Cp; h->Cc = q.Cc; h->n_tiles = q.n_tiles; h->pair_g = q.pair_g;
     h->dt_bytes = q.dt_bytes;
     h->dt_dev[0] = h->dt_dev[1] = nullptr;
     h->stride = 1; h->phased = false; h->zsum_dev = nullptr; h->w8_dev = nullptr; h->lut = lut;
@@ -953,7 +979,7 @@ static int weights_pack(adapt_weights **out, const adapt_lut *lut, const int8_t 
 static LinesShape shape_of(const adapt_weights *h) {
     LinesShape q;
     q.kind = h->kind; q.N = h->N; q.Cin = h->Cin; q.kh = h->kh; q.kw = h->kw;
-    q.Cp = h->Cp; q.Cc = h->Cc; q.n_tiles = h->n_tiles; q.dt_bytes = h->dt_bytes;
+    q.Cp = h->Cp; q.Cc = h->Cc; q.n_tiles = h->n_tiles; q.dt_bytes = h->dt_bytes; q.pair_g = h->pair_g;
     return q;
 }
 
@@ -989,7 +1015,7 @@ int adapt_weights_pack_conv_transpose2d(adapt_weights **out, const adapt_lut *lu
     if (!h) return fail(ADAPT_ERR_OUT_OF_MEMORY, "%s: host allocation failed", who);
     h->kind = 2; h->bits = lut->bits; h->storage = lut->storage; h->device = lut->device;
     h->N = Cout; h->Cin = Cin; h->kh = kh; h->kw = kw; h->stride = stride;
-    h->Cp = h->Cc = h->n_tiles = 0; h->dt_bytes = 0;
+    h->Cp = h->Cc = h->n_tiles = 0; h->dt_bytes = 0; h->pair_g = 0;
     h->dt_dev[0] = h->dt_dev[1] = nullptr;
     h->zsum_dev = nullptr; h->w8_dev = nullptr; h->lut = lut;
     h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0;

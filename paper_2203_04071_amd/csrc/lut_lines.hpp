@@ -72,6 +72,11 @@ struct LinesParams {
     // reduce_partials_kernel adds the slices up.  ksplit == 1: no split.
     int ksplit, gps;
     long long ks_out_stride;
+    // Tap pairing (fast kernel, PAIRED): layers with fewer than 32 (padded) channels per tap put pair_g = 32 / Cp taps
+    // side by side in a group of four steps: k-sub j serves tap pair_g * group + j / pair_cg and the four channels
+    // 4 * (j % pair_cg) + step of it (pair_cg = Cp / 4).  `taps` then counts groups and Cc is 4; taps_real is the
+    // number of filter taps (taps beyond it are padding: all-zero tables).
+    int pair_g, pair_cg, taps_real;
 };
 
 // what is stored for the finished sum v of output channel n (see LinesParams::deq)
@@ -182,12 +187,14 @@ __global__ __launch_bounds__(256) void rows_to_xmajor_kernel(const Src a, int8_t
 // Derived tables.  lut16: [2^b][2^b] 16-bit entries, index [a & mask][w & mask] (two's-complement
 // wrap of the signed operands, so activation 0 is line 0).  One thread writes the 8 channel entries
 // of (n-tile, step, line a, k-sub j).  wmode 0: w[n][K] / [Cout][Cin][taps]; wmode 1: [Cin][Cout][taps].
+// pair_g > 0: tap pairing (see LinesParams): step = 4 * group + t, k-sub j holds tap pair_g * group + j / pair_cg,
+// channel 4 * (j % pair_cg) + t; `steps` is then 4 * number of groups, else taps * Cc.
 __global__ void pack_line_tables_kernel(const uint16_t *__restrict__ lut16, const int8_t *__restrict__ w,
                                         uint4 *__restrict__ dt, int bits, int N, int Cin, int taps, int Cc,
-                                        int n_tiles, int wmode) {
+                                        int n_tiles, int wmode, int pair_g, int pair_cg) {
     const int lines = 1 << bits, mask = lines - 1;
     const size_t per_table = (size_t)lines * 8;
-    const size_t steps = (size_t)taps * Cc;
+    const size_t steps = pair_g > 0 ? (size_t)((taps + pair_g - 1) / pair_g) * 4 : (size_t)taps * Cc;
     const size_t total = (size_t)n_tiles * steps * per_table;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
@@ -196,14 +203,20 @@ __global__ void pack_line_tables_kernel(const uint16_t *__restrict__ lut16, cons
         const size_t ts = i / per_table;
         const int step = (int)(ts % steps);
         const int nt = (int)(ts / steps);
-        const int tap = step / Cc, t = step - tap * Cc;
-        const int ci = j * Cc + t;
+        int tap, ci;
+        if (pair_g > 0) {
+            tap = pair_g * (step >> 2) + j / pair_cg;
+            ci = 4 * (j % pair_cg) + (step & 3);
+        } else {
+            tap = step / Cc;
+            ci = j * Cc + (step - tap * Cc);
+        }
         uint32_t e[8];
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
             const int n = nt * 8 + c;
             uint32_t v = 0;
-            if (n < N && ci < Cin) {
+            if (n < N && ci < Cin && tap < taps) {
                 const size_t wi = wmode == 0 ? ((size_t)n * Cin + ci) * taps + tap : ((size_t)ci * N + n) * taps + tap;
                 v = lut16[(size_t)a * lines + ((int)w[wi] & mask)];
             }
@@ -679,7 +692,7 @@ __device__ __forceinline__ void row_fetch(u32x4_t &v, uint32_t word, uint32_t bi
 // u = 2 (which also guarantees A(g+1), needed by the fetches of u = 3) and of u = 3.  The last two
 // groups issue fewer operations and simply wait for everything.
 // ---------------------------------------------------------------------------------------------
-template <int R, bool SIGNED, bool REGULAR, bool TWO_OPS, bool XMAJOR>
+template <int R, bool SIGNED, bool REGULAR, bool TWO_OPS, bool XMAJOR, bool PAIRED = false>
 __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const LinesParams p) {
     __shared__ uint4 tbl[4 * TABLE_U4_MAX];          // 128 KB
     constexpr int D = TWO_OPS ? 2 : 1;
@@ -762,6 +775,10 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
         if (b == p.Wo) { b = 0; ++a; }
         if (a * p.Wo == p.HoWo) { a = 0; ++img; }
     };
+    // first inner index of this lane's k-sub inside a tap, as a byte offset: PAIRED channel group j % pair_cg, else
+    // the j-th run of Cc channels
+    const int ksub_ch = PAIRED ? 4 * (j % p.pair_cg) : j * p.Cc;
+    const int ksub_off = XMAJOR ? ksub_ch * p.ch_stride : ksub_ch;
     {
         int r0 = mt * (128 * R) + rs * R;
         if (REGULAR && r0 > p.M - R) r0 = p.M - R;
@@ -770,8 +787,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
             row_pos(r0, img, a, b);
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                base[i] = (uint32_t)((long long)img * p.img_stride + (long long)a * p.oy_stride + (long long)b * p.ox_stride +
-                                     j * p.Cc * p.ch_stride);
+                base[i] = (uint32_t)((long long)img * p.img_stride + (long long)a * p.oy_stride + (long long)b * p.ox_stride + ksub_off);
                 next_run(img, a, b);
             }
         } else {
@@ -781,7 +797,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
                 if (r >= p.M) r = p.M - 1;
                 int img, a, b;
                 row_pos(r, img, a, b);
-                base[i] = (uint32_t)((long long)img * p.img_stride + (long long)a * p.oy_stride + (long long)b * p.ox_stride + j * p.Cc);
+                base[i] = (uint32_t)((long long)img * p.img_stride + (long long)a * p.oy_stride + (long long)b * p.ox_stride + ksub_off);
             }
         }
         if (REGULAR) row_step = p.HoWo == 1 ? (uint32_t)p.img_stride : (uint32_t)p.ox_stride;
@@ -793,16 +809,19 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
         uint32_t w[XMAJOR ? 1 : R];
         __device__ __forceinline__ uint32_t row(int i) const { return XMAJOR ? q[i / 4][i % 4] : w[i]; }
     };
-    auto load_acts = [&](Acts &a, const int8_t *xrow) {
+    // lane_off: per-lane part of the tap offset (PAIRED; else 0)
+    auto load_acts = [&](Acts &a, const int8_t *xrow, uint32_t lane_off) {
         if constexpr (XMAJOR) {     // 4 consecutive pixels x 4 channel bytes are 16 contiguous bytes
+            const uint32_t b0 = base[0] + lane_off, b1 = base[NB - 1] + lane_off;
             asm volatile("global_load_dwordx4 %[a0], %[b0], %[xr]\n\tglobal_load_dwordx4 %[a1], %[b1], %[xr]"
                          : [a0] "+v"(a.q[0]), [a1] "+v"(a.q[1])
-                         : [b0] "v"(base[0]), [b1] "v"(base[NB - 1]), [xr] "s"(xrow));
+                         : [b0] "v"(b0), [b1] "v"(b1), [xr] "s"(xrow));
         } else {
 #pragma unroll
             for (int i = 0; i < R; ++i) {
                 const int8_t *srow = REGULAR ? xrow + (size_t)i * row_step : xrow;
-                asm volatile("global_load_dword %[a0], %[b0], %[xr]" : [a0] "+v"(a.w[i]) : [b0] "v"(base[REGULAR ? 0 : i]), [xr] "s"(srow));
+                const uint32_t b0 = base[REGULAR ? 0 : i] + lane_off;
+                asm volatile("global_load_dword %[a0], %[b0], %[xr]" : [a0] "+v"(a.w[i]) : [b0] "v"(b0), [xr] "s"(srow));
             }
         }
     };
@@ -811,19 +830,63 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     auto step_end = [&](auto imm) {
         asm volatile("s_waitcnt %[im]\n\ts_barrier" : : [im] "n"(decltype(imm)::value) : "memory");
     };
+    // aw = awn at the end of a group, as a statement of its own: left to the compiler, the copy could be scheduled
+    // ahead of the wait that covers the loads into awn (it believes awn complete since the load statement)
+    auto take_next = [&](Acts &dst, const Acts &src) {
+        if constexpr (XMAJOR) {
+            uint32_t t[8];
+            asm volatile("v_mov_b32 %0, %8\n\tv_mov_b32 %1, %9\n\tv_mov_b32 %2, %10\n\tv_mov_b32 %3, %11\n\t"
+                         "v_mov_b32 %4, %12\n\tv_mov_b32 %5, %13\n\tv_mov_b32 %6, %14\n\tv_mov_b32 %7, %15"
+                         : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]), "=&v"(t[6]), "=&v"(t[7])
+                         : "v"(src.q[0].x), "v"(src.q[0].y), "v"(src.q[0].z), "v"(src.q[0].w), "v"(src.q[1].x), "v"(src.q[1].y),
+                           "v"(src.q[1].z), "v"(src.q[1].w));
+            dst.q[0] = u32x4_t{t[0], t[1], t[2], t[3]};
+            dst.q[1] = u32x4_t{t[4], t[5], t[6], t[7]};
+        } else {
+#pragma unroll
+            for (int i = 0; i < R; ++i) asm volatile("v_mov_b32 %0, %1" : "=v"(dst.w[i]) : "v"(src.w[i]));
+        }
+    };
 
     uint32_t acc[R * 8];
 #pragma unroll
     for (int q = 0; q < R * 8; ++q) acc[q] = 0;
 
-    // position of the NEXT group's activations (starts at this slice's first group)
-    const int tap0 = (g_begin << 2) / p.Cc;
+    // position of the NEXT group's activations (starts at this slice's first group).  Unpaired: all lanes are in the
+    // same tap, (kx, t4) and the offsets are uniform.  PAIRED: a lane's tap is pair_g * group + j / pair_cg, so its
+    // filter position and offset live in vector registers and advance by pair_g taps per group; taps past the last
+    // one (padding, all-zero tables) read offset 0.
+    const int tap0 = PAIRED ? 0 : (g_begin << 2) / p.Cc;
     const int ky0 = tap0 / p.kw;
-    int kx = tap0 - ky0 * p.kw, t4 = (g_begin << 2) - tap0 * p.Cc;
+    int kx = tap0 - ky0 * p.kw, t4 = PAIRED ? 0 : (g_begin << 2) - tap0 * p.Cc;
     int t4off = XMAJOR ? t4 * p.ch_stride : t4;                 // byte offset of inner index t4 within a tap
     uint32_t rowoff = (uint32_t)(ky0 * p.ky_stride);            // ky * ky_stride
     uint32_t tapoff = rowoff + (uint32_t)(kx * p.kx_stride);    // + kx * kx_stride; both advance by additions
+    int ltap = 0, lkx = 0;
+    uint32_t loff = 0;
+    if constexpr (PAIRED) {
+        ltap = p.pair_g * g_begin + j / p.pair_cg;
+        const int lky = ltap / p.kw;
+        lkx = ltap - lky * p.kw;
+        loff = (uint32_t)(lky * p.ky_stride + lkx * p.kx_stride);
+    }
+    auto lane_off = [&]() -> uint32_t { return PAIRED ? (ltap < p.taps_real ? loff : 0u) : 0u; };
     auto advance_group = [&]() {
+        if constexpr (PAIRED) {
+            // pair_g (2 or 4) single-tap steps, written without branches
+            const uint32_t wrap = (uint32_t)(p.ky_stride - p.kw * p.kx_stride);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const bool on = q < p.pair_g;
+                lkx += on ? 1 : 0;
+                loff += on ? (uint32_t)p.kx_stride : 0u;
+                const bool w = lkx == p.kw;
+                loff += w ? wrap : 0u;
+                lkx = w ? 0 : lkx;
+            }
+            ltap += p.pair_g;
+            return;
+        }
         t4 += 4;
         t4off += XMAJOR ? 4 * p.ch_stride : 4;
         if (t4 == p.Cc) {
@@ -854,7 +917,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     dma(0, 0);
     dma(1, 1);
     dma(2, 2);
-    load_acts(aw, xt + tapoff + t4off);
+    load_acts(aw, PAIRED ? xt : xt + tapoff + t4off, lane_off());
     step_end(std::integral_constant<int, WAIT_ALL>{});
     advance_group();
     // first-half entries of step 0
@@ -866,7 +929,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
         // u = 0: table buffers 0 (this step) and 1 (next step); activations of the next group (after the last group:
         // those of the first one again, unused)
         dma(s0 + 3, 3);
-        load_acts(awn, g + 1 < groups ? xt + tapoff + t4off : xt);
+        load_acts(awn, (!PAIRED && g + 1 < groups) ? xt + tapoff + t4off : xt, g + 1 < groups ? lane_off() : 0u);
 #pragma unroll
         for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + i * 8, rv[i]); row_fetch<0, 0>(rv[i], aw.row(H + i), ubits, cb0); }
 #pragma unroll
@@ -894,7 +957,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
 #pragma unroll
         for (int i = 0; i < H; ++i) { row_add<SIGNED, WN>(acc + (H + i) * 8, rv[i]); row_fetch<0, 0>(rv[i], awn.row(i), ubits, cb0); }
         step_end(std::integral_constant<int, WAIT_D>{});
-        aw = awn;
+        take_next(aw, awn);
         advance_group();
     }
     // retire the reads and copies issued past the end before the compiler may reuse their registers
