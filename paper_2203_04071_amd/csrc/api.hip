@@ -11,6 +11,7 @@
 #include "../../include/adapt_mi355.h"
 #include "elementwise.hpp"
 #include "lut_lines.hpp"
+#include "lut_wide.hpp"
 #include "lut_rows.hpp"
 
 namespace {
@@ -126,6 +127,9 @@ struct adapt_weights {
     int wofs_npad;
     uint32_t *wofs1_dev;
     int wofs1_npad;
+    // The same derived tables in the wide order (lut_wide.hpp), made on first use by a call whose geometry takes the
+    // wide-line kernel (single-pass tables, 32 | padded channels); from the handle's copy of the weights.
+    mutable uint4 *dtw_dev;
 };
 
 extern "C" {
@@ -399,6 +403,15 @@ int launch_lines_xmajor(const adapt::LinesParams &p, unsigned grid, hipStream_t 
     return ADAPT_OK;
 }
 
+// wide-line kernel: 8 rows per lane from an x-major copy, signed single-pass tables
+int launch_lines_wide(const adapt::LinesParams &p, unsigned grid, hipStream_t s) {
+    if (p.bits == 8) adapt::lut_lines_wide_kernel<4><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    else if (p.bits == 7) adapt::lut_lines_wide_kernel<2><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    else adapt::lut_lines_wide_kernel<1><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
 template <int R>
 int launch_lines_r(const adapt::LinesParams &p, unsigned grid, bool sgn, bool regular, hipStream_t s) {
     if (p.Cc % 4 == 0) {       // groups of four steps never straddle a filter tap: fully unrolled variant
@@ -458,6 +471,9 @@ struct LinesCall {       // per-call geometry of the activation side
     int xmajor, ch_stride;  // x-major activation copy (see pad_channels_last_kernel) and its bytes per channel step
     int out_plane, out_sy, out_sx;      // see adapt::LinesParams
     std::vector<LinesPhase> phases;
+    // Derived tables in the wide order (lut_wide.hpp) for the x-major case, or nullptr.  Callers only provide it for
+    // single-pass tables without tap pairing.
+    const uint4 *dt_wide = nullptr;
     int32_t *partial = nullptr;         // room for the partial sums when the plan splits the inner dimension
     size_t out_elems = 0;               // elements of the whole output tensor
     size_t out_channels = 1, out_inner = 1;     // where the channel sits in a flat output index: (i / inner) % channels
@@ -546,7 +562,10 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
             }
             const long long grid = (long long)p.m_tiles * q.n_tiles * p.phases * p.ksplit;
             if (grid > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "lines path: grid too large");
-            if (xmajor) rc = sgn ? launch_lines_xmajor<true>(p, (unsigned)grid, s) : launch_lines_xmajor<false>(p, (unsigned)grid, s);
+            if (xmajor && c.dt_wide && storage == 0 && !q.pair_g) {
+                p.dt = c.dt_wide;
+                rc = launch_lines_wide(p, (unsigned)grid, s);
+            } else if (xmajor) rc = sgn ? launch_lines_xmajor<true>(p, (unsigned)grid, s) : launch_lines_xmajor<false>(p, (unsigned)grid, s);
             else if (R == 8) rc = launch_lines_r<8>(p, (unsigned)grid, sgn, regular, s);
             else if (R == 4) rc = launch_lines_r<4>(p, (unsigned)grid, sgn, regular, s);
             else rc = launch_lines_r<2>(p, (unsigned)grid, sgn, regular, s);
@@ -562,11 +581,41 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     return rc;
 }
 
+// Derived tables of a packed handle in the wide order, made on first use; nullptr when the handle's shape has none
+// (two-pass table, paired taps, channels per tap not a multiple of 32) or memory is short (the caller then stays on
+// the lines kernels).
+const uint4 *ensure_wide(const adapt_weights *h, hipStream_t s) {
+    if (!h) return nullptr;
+    if (h->dtw_dev) return h->dtw_dev;
+    if (h->storage != 0 || h->pair_g || !h->w8_dev || !h->lut || h->Cc % 4 != 0 || h->dt_bytes == 0) return nullptr;
+    uint4 *d = nullptr;
+    if (hipMalloc((void **)&d, h->dt_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    const size_t total = h->dt_bytes / 16;
+    size_t blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    if (h->kind == 2)
+        adapt::pack_wide_tables_convt_kernel<<<(unsigned)blocks, 256, 0, s>>>(h->lut->lut16_dev[0], h->w8_dev, d, h->bits, h->N, h->Cin, h->kh,
+                                                                             h->kw, h->stride, h->Cp, h->n_tiles);
+    else
+        adapt::pack_wide_tables_kernel<<<(unsigned)blocks, 256, 0, s>>>(h->lut->lut16_dev[0], h->w8_dev, d, h->bits, h->N, h->Cin,
+                                                                       h->kh * h->kw, h->Cp, h->n_tiles, 0);
+    if (hipGetLastError() != hipSuccess) {
+        (void)hipFree(d);
+        return nullptr;
+    }
+    h->dtw_dev = d;
+    return d;
+}
+
 // activation side of a linear layer: A itself when its rows are a multiple of 32 bytes, else a zero-padded copy
 int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *a, int32_t *out, int M, hipStream_t s,
-                 Workspace *ws, const LayerIO *io = nullptr) {
-    const adapt::SrcI8 src8{a};
-    const adapt::SrcF32 srcf{io ? io->xf : nullptr, io ? io->s_x : 1.0f, io ? io->Q : 1.0f};
+                 Workspace *ws, const LayerIO *io = nullptr, const adapt_weights *wh = nullptr) {
+    const uint32_t amask = (1u << bits) - 1u;
+    const adapt::SrcI8 src8{a, amask};
+    const adapt::SrcF32 srcf{io ? io->xf : nullptr, io ? io->s_x : 1.0f, io ? io->Q : 1.0f, amask};
     const bool from_f32 = io && io->xf;
     const int K = q.Cin, Kp = q.Cp;
     int8_t *tmp = nullptr;
@@ -590,6 +639,7 @@ int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
         c.oy_stride = c.ky_stride = 0; c.ox_stride = c.kx_stride = 4;
         c.xmajor = 1; c.ch_stride = M;
         c.out_plane = 1; c.out_sy = 0; c.out_sx = q.N;
+        c.dt_wide = ensure_wide(wh, s);
     } else {
         if (Kp != K || from_f32 || part_bytes) {
             int wrc = ws_get(ws, copy_bytes + part_bytes, s, (void **)&tmp);
@@ -618,7 +668,7 @@ int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
 // activation side of a convolution: zero-padded channel-last copy of x
 int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *x, int32_t *out, int N, int H,
                  int W, int Ho, int Wo, int sh, int sw, int ph, int pw, int dh, int dw, hipStream_t s, Workspace *ws,
-                 const LayerIO *io = nullptr) {
+                 const LayerIO *io = nullptr, const adapt_weights *wh = nullptr) {
     const int Hp = H + 2 * ph, Wp = W + 2 * pw, Cp = q.Cp;
     const size_t xt_bytes = (size_t)N * Hp * Wp * Cp;
     // With 8 rows per lane that are 8 consecutive output pixels of a stride-1 convolution, the copy is laid
@@ -637,9 +687,9 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
         size_t blocks = (total + 255) / 256;
         if (blocks > 65536) blocks = 65536;
         if (io && io->xf)
-            adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcF32{io->xf, io->s_x, io->Q}, xt, N, q.Cin, H, W, ph,
+            adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcF32{io->xf, io->s_x, io->Q, (1u << bits) - 1u}, xt, N, q.Cin, H, W, ph,
                                                                              pw, Cp, xmajor);
-        else adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcI8{x}, xt, N, q.Cin, H, W, ph, pw, Cp, xmajor);
+        else adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcI8{x, (1u << bits) - 1u}, xt, N, q.Cin, H, W, ph, pw, Cp, xmajor);
     }
     LinesCall c;
     c.M = M; c.HoWo = Ho * Wo; c.Wo = Wo;
@@ -652,6 +702,7 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     c.phases.resize(1);
     c.out_elems = out_elems; c.out_channels = (size_t)q.N; c.out_inner = (size_t)Ho * Wo;
     if (part_bytes) c.partial = reinterpret_cast<int32_t *>(xt + copy_bytes);
+    if (xmajor) c.dt_wide = ensure_wide(wh, s);
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io);
     rc = ws_put(ws, xt, s, rc);
     if (rc == ADAPT_OK && io && io->deq && !io->fused(storage))
@@ -671,7 +722,7 @@ LinesShape convt_phase_shape(int bits, int Cout, int Cin, int kh, int kw, int st
 
 int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int32_t *zsum, const int8_t *x,
                            int32_t *out, int N, int H, int W, int kh, int kw, int st, int pad, hipStream_t s, Workspace *ws,
-                           const LayerIO *io = nullptr) {
+                           const LayerIO *io = nullptr, const adapt_weights *wh = nullptr) {
     const int Ty = q.kh, Tx = q.kw, Cp = q.Cp;
     const int Hp = H + 2 * (Ty - 1), Wp = W + 2 * (Tx - 1);
     const int Ho = (H - 1) * st - 2 * pad + kh, Wo = (W - 1) * st - 2 * pad + kw;
@@ -690,9 +741,9 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
         size_t blocks = (total + 255) / 256;
         if (blocks > 65536) blocks = 65536;
         if (io && io->xf)
-            adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcF32{io->xf, io->s_x, io->Q}, xt, N, q.Cin, H, W,
+            adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcF32{io->xf, io->s_x, io->Q, (1u << bits) - 1u}, xt, N, q.Cin, H, W,
                                                                              Ty - 1, Tx - 1, Cp, xmajor);
-        else adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcI8{x}, xt, N, q.Cin, H, W, Ty - 1, Tx - 1, Cp, xmajor);
+        else adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcI8{x, (1u << bits) - 1u}, xt, N, q.Cin, H, W, Ty - 1, Tx - 1, Cp, xmajor);
     }
     LinesCall c;
     c.M = M; c.HoWo = Qy * Qx; c.Wo = Qx;
@@ -718,6 +769,7 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
     const bool border = Ly > 0 || Lx > 0;       // then the sums are corrected before they can be rescaled
     c.out_elems = out_elems; c.out_channels = (size_t)q.N; c.out_inner = (size_t)Ho * Wo;
     if (part_bytes) c.partial = reinterpret_cast<int32_t *>(xt + copy_bytes);
+    if (xmajor) c.dt_wide = ensure_wide(wh, s);
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io, !border);
     rc = ws_put(ws, xt, s, rc);
     if (rc != ADAPT_OK) return rc;
@@ -946,7 +998,17 @@ static int weights_pack(adapt_weights **out, const adapt_lut *lut, const int8_t 
     h->dt_bytes = q.dt_bytes;
     h->dt_dev[0] = h->dt_dev[1] = nullptr;
     h->stride = 1; h->phased = false; h->zsum_dev = nullptr; h->w8_dev = nullptr; h->lut = lut;
-    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0;
+    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0; h->dtw_dev = nullptr;
+    {   // copy of the weights (for table orders made later)
+        const size_t wbytes = (size_t)N * Cin * kh * kw;
+        hipError_t e = hipMalloc((void **)&h->w8_dev, wbytes);
+        if (e == hipSuccess) e = hipMemcpyAsync(h->w8_dev, w_dev, wbytes, hipMemcpyDeviceToDevice, (hipStream_t)stream);
+        if (e != hipSuccess) {
+            if (h->w8_dev) (void)hipFree(h->w8_dev);
+            delete h;
+            return fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "%s: copy of the weights: %s", who, hipGetErrorString(e));
+        }
+    }
     if (kind == 0) {
         h->wofs_npad = ((N + 15) / 16) * 16;
         const size_t pack_n = (size_t)Cin * h->wofs_npad;
@@ -1018,7 +1080,7 @@ int adapt_weights_pack_conv_transpose2d(adapt_weights **out, const adapt_lut *lu
     h->Cp = h->Cc = h->n_tiles = 0; h->dt_bytes = 0; h->pair_g = 0;
     h->dt_dev[0] = h->dt_dev[1] = nullptr;
     h->zsum_dev = nullptr; h->w8_dev = nullptr; h->lut = lut;
-    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0;
+    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0; h->dtw_dev = nullptr;
     h->phased = kh % stride == 0 && kw % stride == 0 && stride <= 8;
     const size_t wbytes = (size_t)Cout * Cin * kh * kw;
     hipError_t e = hipMalloc((void **)&h->w8_dev, wbytes);
@@ -1070,6 +1132,7 @@ int adapt_weights_destroy(adapt_weights *h) {
     if (h->ws.ptr) (void)hipFree(h->ws.ptr);
     if (h->wofs_dev) (void)hipFree(h->wofs_dev);
     if (h->wofs1_dev) (void)hipFree(h->wofs1_dev);
+    if (h->dtw_dev) (void)hipFree(h->dtw_dev);
     if (h->zsum_dev) (void)hipFree(h->zsum_dev);
     if (h->w8_dev) (void)hipFree(h->w8_dev);
     delete h;
@@ -1093,7 +1156,7 @@ int adapt_approx_conv_transpose2d_packed(const adapt_weights *h, const int8_t *x
         const long long xt_bytes = (long long)N * (H + 2LL * (q.kh - 1)) * (W + 2LL * (q.kw - 1)) * q.Cp;
         if (xt_bytes < 0x7fffff00LL)
             return lines_conv_transpose2d(h->bits, h->storage, q, h->dt_dev, h->zsum_dev, x_dev, acc_dev, N, H, W, h->kh, h->kw,
-                                          h->stride, pad, (hipStream_t)stream, &h->ws);
+                                          h->stride, pad, (hipStream_t)stream, &h->ws, nullptr, h);
     }
     // geometries outside the phase form (a single input pixel, output sizes that are no multiple of the stride)
     return convt_rows(h->lut, x_dev, h->w8_dev, acc_dev, N, h->Cin, H, W, h->N, h->kh, h->kw, h->stride, pad, (hipStream_t)stream, h);
@@ -1114,7 +1177,7 @@ int adapt_approx_linear_packed(const adapt_weights *h, const int8_t *a_dev, int3
         g.kstride = 1; g.img_stride = h->Cin;
         return run_rows(h->lut, a_dev, nullptr, acc_dev, g, (hipStream_t)stream, h->wofs_dev, h->wofs_npad);
     }
-    return lines_linear(h->bits, h->storage, shape_of(h), h->dt_dev, a_dev, acc_dev, M, (hipStream_t)stream, &h->ws);
+    return lines_linear(h->bits, h->storage, shape_of(h), h->dt_dev, a_dev, acc_dev, M, (hipStream_t)stream, &h->ws, nullptr, h);
 }
 
 int adapt_approx_conv2d_packed(const adapt_weights *h, const int8_t *x_dev, int32_t *acc_dev, int N, int H, int W, int stride_h,
@@ -1133,7 +1196,7 @@ int adapt_approx_conv2d_packed(const adapt_weights *h, const int8_t *x_dev, int3
     if (xt_bytes >= 0x7fffff00LL || (long long)N * h->N * Ho * Wo > 0x7fffffffLL || (long long)N * Ho * Wo > 0x7fffffffLL)
         return fail(ADAPT_ERR_UNSUPPORTED, "adapt_approx_conv2d_packed: tensor with more than 2^31-1 elements");
     return lines_conv2d(h->bits, h->storage, shape_of(h), h->dt_dev, x_dev, acc_dev, N, H, W, (int)Ho, (int)Wo, stride_h, stride_w,
-                        pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream, &h->ws);
+                        pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream, &h->ws, nullptr, h);
 }
 
 /* ------------------------------------------------------------------ whole layers, fp32 in and out */
@@ -1180,7 +1243,7 @@ int adapt_linear_layer_f32(const adapt_weights *h, const float *x_dev, float *y_
         g.kstride = 1; g.img_stride = h->Cin;
         return run_rows(h->lut, q, nullptr, out, g, s, h->wofs_dev, h->wofs_npad, &io);
     }
-    return lines_linear(h->bits, h->storage, shape_of(h), h->dt_dev, nullptr, out, M, s, &h->ws, &io);
+    return lines_linear(h->bits, h->storage, shape_of(h), h->dt_dev, nullptr, out, M, s, &h->ws, &io, h);
 }
 
 int adapt_conv2d_layer_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W, int stride_h, int stride_w,
@@ -1202,7 +1265,7 @@ int adapt_conv2d_layer_f32(const adapt_weights *h, const float *x_dev, float *y_
     if (xt_bytes >= 0x7fffff00LL || (long long)N * h->N * Ho * Wo > 0x7fffffffLL || (long long)N * Ho * Wo > 0x7fffffffLL)
         return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
     return lines_conv2d(h->bits, h->storage, shape_of(h), h->dt_dev, nullptr, reinterpret_cast<int32_t *>(y_dev), N, H, W, (int)Ho,
-                        (int)Wo, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream, &h->ws, &io);
+                        (int)Wo, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream, &h->ws, &io, h);
 }
 
 int adapt_conv_transpose2d_layer_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W, int pad, float s_x,
@@ -1225,7 +1288,7 @@ int adapt_conv_transpose2d_layer_f32(const adapt_weights *h, const float *x_dev,
         const long long xt_bytes = (long long)N * (H + 2LL * (q.kh - 1)) * (W + 2LL * (q.kw - 1)) * q.Cp;
         if (xt_bytes < 0x7fffff00LL)
             return lines_conv_transpose2d(h->bits, h->storage, q, h->dt_dev, h->zsum_dev, nullptr, out, N, H, W, h->kh, h->kw, h->stride,
-                                          pad, s, &h->ws, &io);
+                                          pad, s, &h->ws, &io, h);
     }
     int8_t *q8 = nullptr;
     if ((rc = quantize_into_ws(h, io, (size_t)N * h->Cin * H * W, s, &q8))) return rc;

@@ -95,15 +95,19 @@ __device__ __forceinline__ T pick4(const T *v, int i) {
 }
 
 // Activation sources of the copy kernels: already quantised int8, or fp32 quantised on the fly with the quantiser of
-// quantize_kernel (Sec. III-A), so that a layer needs no separate quantisation pass.
+// quantize_kernel (Sec. III-A), so that a layer needs no separate quantisation pass.  The copies hold table line
+// indices (the kernels that extract a bit field do not care, the wide-line kernel relies on it).
+// byte(): the operand as a table line index, i.e. its two's-complement bits below 2^b (mask = 2^b - 1)
 struct SrcI8 {
     const int8_t *x;
-    __device__ __forceinline__ uint32_t byte(size_t i) const { return (uint32_t)(uint8_t)x[i]; }
+    uint32_t mask;
+    __device__ __forceinline__ uint32_t byte(size_t i) const { return (uint32_t)(uint8_t)x[i] & mask; }
 };
 struct SrcF32 {
     const float *x;
     float scale, Q;
-    __device__ __forceinline__ uint32_t byte(size_t i) const { return (uint32_t)quant1(x[i], scale, Q) & 0xffu; }
+    uint32_t mask;
+    __device__ __forceinline__ uint32_t byte(size_t i) const { return (uint32_t)quant1(x[i], scale, Q) & mask; }
 };
 
 // NCHW int8 -> zero-padded copy, Cp (a multiple of 8) channels per pixel, in one of two orders:
@@ -166,7 +170,7 @@ __global__ __launch_bounds__(256) void rows_to_xmajor_kernel(const Src a, int8_t
         uint32_t v = 0;
         if (m < M) {
             if (fast) {
-                if (k < K) v = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const int8_t *>(a.x) + (size_t)m * K + k);
+                if (k < K) v = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const int8_t *>(a.x) + (size_t)m * K + k) & (a.mask * 0x01010101u);
             } else {
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
