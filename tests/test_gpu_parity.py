@@ -325,6 +325,27 @@ def test_config2_conv_full_size(B):
     assert_f32_close(host(y), orc.dequant(want, np.float32(s_x) * np.float32(s_w), 32, 64, 1024))
 
 
+def test_config2_fused_layer_full_size_as_benchmarked(B):
+    """The launch configuration bench.py times at config 2: one fused layer call on packed weights (quantise while the
+    input is laid out, wide-line kernel, rescaling in its epilogue), whole tensor against the oracle."""
+    c = wl.config2()
+    bits = 8
+    th = orc.host_threads()
+    s_x = orc.scale_from_amax(orc.absmax(c["x"]), bits)
+    s_w = orc.scale_from_amax(orc.absmax(c["w"]), bits)
+    oqw = orc.quantize(c["w"], s_w, bits)
+    want_acc = orc.approx_conv2d(c["lut"], bits, orc.quantize(c["x"], s_x, bits), oqw, (1, 1), (1, 1), threads=th)
+    s_out = np.float32(s_x) * np.float32(s_w)
+    want = orc.dequant(want_acc, s_out, 32, 64, 1024)
+    L = B.Lut(c["lut"], bits)
+    pw = B.adapt_weights_pack_conv2d(L, dev(oqw))
+    x = dev(c["x"])
+    for rep in range(2):
+        got = host(B.adapt_conv2d_layer_f32(pw, x, s_x, s_out, (1, 1), (1, 1)))
+        assert bits_equal(got.reshape(want.shape), want), rep
+    assert (host(B.adapt_approx_conv2d_packed(pw, dev(orc.quantize(c["x"], s_x, bits)), (1, 1), (1, 1))) == want_acc).all()
+
+
 def test_config3_resnet20_full_size(B):
     from paper_2203_04071_amd import networks as gnet
     c = wl.config3()
