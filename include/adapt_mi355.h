@@ -209,6 +209,16 @@ int adapt_lstm_cell_q_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, 
                           const float *bias_dev, float *c_dev, float *h_dev, int8_t *qh_dev, float s_h, int bits, int B,
                           int Hs, void *stream);
 
+/* One whole time step of the recurrent part of an LSTM layer in one kernel:
+ *     acc_hh = table product of qh_dev [B][Hs] with the packed W_hh [4 Hs][Hs]   (adapt_approx_linear_packed)
+ *     (c, h) = cell(acc_ih, acc_hh);  qh_next = quantise(h, s_h)                   (adapt_lstm_cell_q_f32)
+ * with the same integers and floats as those two calls.  w_hh: handle of adapt_weights_pack_linear for W_hh.
+ * acc_ih_dev [B][4 Hs]; c_dev [B][Hs] in place; h_dev [B][Hs]; qh_next_dev [B][Hs], must not alias qh_dev.
+ * Covers even Hs and single-pass tables; otherwise ADAPT_ERR_UNSUPPORTED and the caller uses the two calls above. */
+int adapt_lstm_step_f32(const adapt_weights *w_hh, const int8_t *qh_dev, const int32_t *acc_ih_dev, float s_ih, float s_hh,
+                        float s_h, const float *bias_dev, float *c_dev, float *h_dev, int8_t *qh_next_dev, int B, int Hs,
+                        void *stream);
+
 #ifdef __cplusplus
 }
 #endif

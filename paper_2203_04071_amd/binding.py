@@ -29,7 +29,7 @@ EXPORTS = [
     "adapt_approx_linear_packed", "adapt_approx_conv2d_packed", "adapt_approx_conv_transpose2d_packed",
     "adapt_linear_layer_f32", "adapt_conv2d_layer_f32", "adapt_conv_transpose2d_layer_f32",
     "adapt_relu_f32", "adapt_add_f32", "adapt_avgpool_hw_f32", "adapt_shortcut_a_f32",
-    "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32", "adapt_lstm_cell_q_f32",
+    "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32", "adapt_lstm_cell_q_f32", "adapt_lstm_step_f32",
 ]
 
 
@@ -82,6 +82,7 @@ def load() -> ctypes.CDLL:
     L.adapt_tanh_f32.argtypes = [vp, vp, sz, vp]
     L.adapt_sigmoid_f32.argtypes = [vp, vp, sz, vp]
     L.adapt_lstm_cell_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, i32, i32, vp]
+    L.adapt_lstm_step_f32.argtypes = [vp, vp, vp, f32, f32, f32, vp, vp, vp, vp, i32, i32, vp]
     L.adapt_lstm_cell_q_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, vp, f32, i32, i32, i32, vp]
     for name in EXPORTS:
         if name != "adapt_last_error":
@@ -409,3 +410,13 @@ def adapt_conv_transpose2d_layer_f32(pw: PackedWeights, x, s_x, s_out, pad=0, bi
     _chk(load().adapt_conv_transpose2d_layer_f32(pw.handle, _ptr(x, torch.float32), _ptr(out, torch.float32), N, H, W, pad,
                                                  float(s_x), float(s_out), _ptr(bias, torch.float32), act, _stream(stream)))
     return out
+
+
+def adapt_lstm_step_f32(pw_hh: PackedWeights, qh, acc_ih, s_ih, s_hh, s_h, bias, c, h, qh_next, stream=None):
+    """Raises AdaptError with code -2 (UNSUPPORTED) when the shape does not fit the fused kernel."""
+    B, H4 = acc_ih.shape
+    Hs = H4 // 4
+    _chk(load().adapt_lstm_step_f32(pw_hh.handle, _ptr(qh, torch.int8), _ptr(acc_ih, torch.int32), float(s_ih), float(s_hh),
+                                    float(s_h), _ptr(bias, torch.float32), _ptr(c, torch.float32), _ptr(h, torch.float32),
+                                    _ptr(qh_next, torch.int8), B, Hs, _stream(stream)))
+    return h, c, qh_next

@@ -130,6 +130,9 @@ struct adapt_weights {
     // The same derived tables in the wide order (lut_wide.hpp), made on first use by a call whose geometry takes the
     // wide-line kernel (single-pass tables, 32 | padded channels); from the handle's copy of the weights.
     mutable uint4 *dtw_dev;
+    // linear [4 Hs][Hs] handles used for LSTM time steps: row offsets with the columns in cell order (see
+    // adapt::RowsParams), made on first use
+    mutable uint32_t *wofs_cell_dev;
 };
 
 extern "C" {
@@ -291,8 +294,18 @@ struct Geometry {
 // Run the rows kernel once per table image of the handle.
 // prepacked: row offsets [K][prepacked_npad] made earlier by pack_row_offsets_kernel (prepacked_npad a multiple of 16),
 // or nullptr to pack `w` into a stream-ordered temporary.
+struct LstmStep {            // see adapt::RowsParams
+    int Hs;
+    const int32_t *acc_ih;
+    const float *bias;
+    float *c, *h;
+    int8_t *qh_next;
+    float s_ih, s_hh, s_h, Qh;
+};
+
 int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *out, const Geometry &g, hipStream_t s,
-             const uint32_t *prepacked = nullptr, int prepacked_npad = 0, const LayerIO *io = nullptr) {
+             const uint32_t *prepacked = nullptr, int prepacked_npad = 0, const LayerIO *io = nullptr,
+             const LstmStep *lstm = nullptr) {
     const int bits = lut->bits;
     const long long Ktot = (long long)g.taps * g.Cin;
     if (g.M == 0 || g.N == 0) return ADAPT_OK;
@@ -312,6 +325,7 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     auto groups = [&](int nt, int mt) { return (long long)((g.M + mt - 1) / mt) * ((g.N + nt - 1) / nt); };
     while (MT > 64 && (MT / 2 >= g.M || (groups(NT, MT) < cu && Ktot / (adapt::ROWS_THREADS / (MT / 2)) >= 16))) MT /= 2;
     if (groups(NT, MT) < cu && g.N > 8) NT = 8;
+    if (lstm) { NT = 8; MT = 64; }      // the cell epilogue sits in the split-K reduction of the 8-column variant
     const int KS = adapt::ROWS_THREADS / MT;
     const int Npad = prepacked ? prepacked_npad : ((g.N + NT - 1) / NT) * NT;
 
@@ -339,6 +353,12 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     p.MT = MT; p.KS = KS;
     const bool fuse = io && io->fused(lut->storage);
     p.deq = fuse ? 1 : 0; p.act = fuse ? io->act : 0; p.scale = fuse ? io->s_out : 1.0f; p.bias = fuse ? io->bias : nullptr;
+    p.lstm = lstm ? 1 : 0; p.Hs = 0; p.acc_ih = nullptr; p.c = p.h = nullptr; p.qh_next = nullptr;
+    p.s_ih = p.s_hh = p.s_h = p.Qh = 1.0f;
+    if (lstm) {
+        p.Hs = lstm->Hs; p.acc_ih = lstm->acc_ih; p.bias = lstm->bias; p.c = lstm->c; p.h = lstm->h; p.qh_next = lstm->qh_next;
+        p.s_ih = lstm->s_ih; p.s_hh = lstm->s_hh; p.s_h = lstm->s_h; p.Qh = lstm->Qh;
+    }
     dim3 grid((unsigned)((g.M + MT - 1) / MT), (unsigned)(Npad / NT));
     size_t lds = (size_t)lut->img_bytes;
     if (KS > 1 && (size_t)adapt::ROWS_THREADS * NT * 4 > lds) lds = (size_t)adapt::ROWS_THREADS * NT * 4;
@@ -998,7 +1018,7 @@ static int weights_pack(adapt_weights **out, const adapt_lut *lut, const int8_t 
     h->dt_bytes = q.dt_bytes;
     h->dt_dev[0] = h->dt_dev[1] = nullptr;
     h->stride = 1; h->phased = false; h->zsum_dev = nullptr; h->w8_dev = nullptr; h->lut = lut;
-    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0; h->dtw_dev = nullptr;
+    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0; h->dtw_dev = nullptr; h->wofs_cell_dev = nullptr;
     {   // copy of the weights (for table orders made later)
         const size_t wbytes = (size_t)N * Cin * kh * kw;
         hipError_t e = hipMalloc((void **)&h->w8_dev, wbytes);
@@ -1080,7 +1100,7 @@ int adapt_weights_pack_conv_transpose2d(adapt_weights **out, const adapt_lut *lu
     h->Cp = h->Cc = h->n_tiles = 0; h->dt_bytes = 0; h->pair_g = 0;
     h->dt_dev[0] = h->dt_dev[1] = nullptr;
     h->zsum_dev = nullptr; h->w8_dev = nullptr; h->lut = lut;
-    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0; h->dtw_dev = nullptr;
+    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0; h->dtw_dev = nullptr; h->wofs_cell_dev = nullptr;
     h->phased = kh % stride == 0 && kw % stride == 0 && stride <= 8;
     const size_t wbytes = (size_t)Cout * Cin * kh * kw;
     hipError_t e = hipMalloc((void **)&h->w8_dev, wbytes);
@@ -1133,6 +1153,7 @@ int adapt_weights_destroy(adapt_weights *h) {
     if (h->wofs_dev) (void)hipFree(h->wofs_dev);
     if (h->wofs1_dev) (void)hipFree(h->wofs1_dev);
     if (h->dtw_dev) (void)hipFree(h->dtw_dev);
+    if (h->wofs_cell_dev) (void)hipFree(h->wofs_cell_dev);
     if (h->zsum_dev) (void)hipFree(h->zsum_dev);
     if (h->w8_dev) (void)hipFree(h->w8_dev);
     delete h;
@@ -1293,6 +1314,44 @@ int adapt_conv_transpose2d_layer_f32(const adapt_weights *h, const float *x_dev,
     int8_t *q8 = nullptr;
     if ((rc = quantize_into_ws(h, io, (size_t)N * h->Cin * H * W, s, &q8))) return rc;
     return convt_rows(h->lut, q8, h->w8_dev, out, N, h->Cin, H, W, h->N, h->kh, h->kw, h->stride, pad, s, h, &io);
+}
+
+/* ------------------------------------------------------------------ LSTM time step in one kernel */
+
+int adapt_lstm_step_f32(const adapt_weights *h, const int8_t *qh_dev, const int32_t *acc_ih_dev, float s_ih, float s_hh, float s_h,
+                        const float *bias_dev, float *c_dev, float *h_dev, int8_t *qh_next_dev, int B, int Hs, void *stream) {
+    const char *who = "adapt_lstm_step_f32";
+    int rc = check_weights(h, 0, who);
+    if (rc) return rc;
+    if (B < 1 || Hs < 1) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
+    if (h->N != 4 * Hs || h->Cin != Hs) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: handle is not a packed [4 Hs][Hs] matrix", who);
+    if (!(s_h > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: s_h must be > 0", who);
+    if (!qh_dev || !acc_ih_dev || !c_dev || !h_dev || !qh_next_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
+    if (qh_dev == qh_next_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: qh_next_dev must not alias qh_dev", who);
+    if (h->storage != 0 || Hs % 2 != 0 || (long long)B * 4 * Hs > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: shape outside the fused kernel (Hs even, single-pass table)", who);
+    hipStream_t s = (hipStream_t)stream;
+    if (!h->wofs_cell_dev) {        // first use: offsets with the columns in cell order, from the handle's copy of the weights
+        const size_t n = (size_t)Hs * 4 * Hs;
+        uint32_t *d = nullptr;
+        HIP_TRY(hipMalloc((void **)&d, n * sizeof(uint32_t)));
+        adapt::pack_row_offsets_cell_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(h->w8_dev, d, Hs, 1 << (h->bits - 1), (1 << h->bits) - 1,
+                                                                                      h->lut->rs * 2);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) {
+            (void)hipFree(d);
+            return fail(ADAPT_ERR_HIP, "%s: pack launch: %s", who, hipGetErrorString(e));
+        }
+        h->wofs_cell_dev = d;
+    }
+    Geometry g{};
+    g.mode = adapt::MODE_GEMM; g.M = B; g.N = 4 * Hs; g.Cin = Hs; g.taps = 1; g.kw = 1;
+    g.H = 1; g.W = 1; g.Wo = 1; g.HoWo = 1; g.sh = g.sw = g.dh = g.dw = 1; g.ph = g.pw = 0;
+    g.kstride = 1; g.img_stride = Hs;
+    LstmStep ls;
+    ls.Hs = Hs; ls.acc_ih = acc_ih_dev; ls.bias = bias_dev; ls.c = c_dev; ls.h = h_dev; ls.qh_next = qh_next_dev;
+    ls.s_ih = s_ih; ls.s_hh = s_hh; ls.s_h = s_h; ls.Qh = (float)((1 << (h->bits - 1)) - 1);
+    return run_rows(h->lut, qh_dev, nullptr, nullptr, g, s, h->wofs_cell_dev, 4 * Hs, nullptr, &ls);
 }
 
 /* ------------------------------------------------------------------ fp32 operations between layers */

@@ -17,6 +17,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "elementwise.hpp"
+
 namespace adapt {
 
 constexpr int ROWS_THREADS = 1024;
@@ -46,6 +48,15 @@ struct RowsParams {
     int deq, act;
     float scale;
     const float *bias;
+    // LSTM time step (lstm != 0; linear layer with N = 4 Hs whose offsets were packed in "cell order": packed column
+    // 8 (u / 2) + 2 g + (u % 2) is gate g of hidden unit u, so the 8 columns of a workgroup are all four gates of two
+    // units): the sums are not stored; the workgroup runs the cell for its two units (the operations of
+    // lstm_cell_kernel) and writes c, h and the quantised h of the next step.
+    int lstm, Hs;
+    const int32_t *acc_ih;      // [M][4 Hs]
+    float *c, *h;               // [M][Hs]
+    int8_t *qh_next;            // [M][Hs]
+    float s_ih, s_hh, s_h, Qh;
 };
 
 __device__ __forceinline__ uint32_t finish_sum(const RowsParams &p, uint32_t v, int n) {
@@ -72,6 +83,19 @@ __global__ void pack_row_offsets_kernel(const int8_t *__restrict__ w, uint32_t *
         v = (uint32_t)(((int)w[wi] + hoff) & mask) * (uint32_t)row_bytes;
     }
     wofs[idx] = v;
+}
+
+// W_hh [4 Hs][Hs] -> row offsets [Hs][4 Hs] with the columns in cell order: packed column 8 (u / 2) + 2 g + (u % 2)
+// holds gate g of hidden unit u, i.e. weight row g * Hs + u
+__global__ void pack_row_offsets_cell_kernel(const int8_t *__restrict__ w, uint32_t *__restrict__ wofs, int Hs, int hoff, int mask,
+                                             int row_bytes) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int N = 4 * Hs;
+    if (idx >= (size_t)Hs * N) return;
+    const int k = (int)(idx / N), cp = (int)(idx % N);
+    const int u = (cp >> 3) * 2 + (cp & 1), g = (cp >> 1) & 3;
+    const size_t wi = ((size_t)g * Hs + u) * Hs + k;
+    wofs[idx] = (uint32_t)(((int)w[wi] + hoff) & mask) * (uint32_t)row_bytes;
 }
 
 template <bool SIGNED>
@@ -218,6 +242,39 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
 #pragma unroll
     for (int n = 0; n < NT; ++n) red[((size_t)ks * NT + n) * p.MT + r_in_tile] = acc[n];
     __syncthreads();
+    if (NT == 8 && p.lstm) {
+        // one thread per (row, unit of the pair): the four gate sums, then the cell
+        for (int o = tid; o < 2 * p.MT; o += ROWS_THREADS) {
+            const int e = o / p.MT, r = o - e * p.MT;
+            const int m2 = blockIdx.x * p.MT + r;
+            if (m2 >= p.M) continue;
+            const int u = blockIdx.y * 2 + e;
+            const size_t ci = (size_t)m2 * p.Hs + u;
+            float pre[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                uint32_t s = 0;
+                for (int j = 0; j < p.KS; ++j) s += red[((size_t)j * NT + g * 2 + e) * p.MT + r];
+                const float uu = (float)p.acc_ih[(size_t)m2 * 4 * p.Hs + (size_t)g * p.Hs + u] * p.s_ih;
+                const float vv = (float)(int32_t)s * p.s_hh;
+                float t = uu + vv;
+                t = t + (p.bias ? p.bias[g * p.Hs + u] : 0.0f);
+                pre[g] = t;
+            }
+            const float ig = sigmoid_spec(pre[0]);
+            const float fg = sigmoid_spec(pre[1]);
+            const float gg = tanh_spec(pre[2]);
+            const float og = sigmoid_spec(pre[3]);
+            const float fc = fg * p.c[ci];
+            const float igg = ig * gg;
+            const float cn = fc + igg;
+            p.c[ci] = cn;
+            const float hn = og * tanh_spec(cn);
+            p.h[ci] = hn;
+            p.qh_next[ci] = (int8_t)quant1(hn, p.s_h, p.Qh);
+        }
+        return;
+    }
     for (int o = tid; o < NT * p.MT; o += ROWS_THREADS) {
         const int n = o / p.MT, r = o - n * p.MT;
         const int m2 = blockIdx.x * p.MT + r;

@@ -124,7 +124,7 @@ class ResNet20:
 
 
 class LSTM:
-    def __init__(self, cfg, device="cuda"):
+    def __init__(self, cfg, device="cuda", fused_step=True):
         self.bits = cfg["bits"]
         self.lut = B.Lut(cfg["lut"], self.bits)
         self.q_wih, self.s_wih = quantize_weights(torch.from_numpy(cfg["w_ih"]).to(device), self.bits)
@@ -134,6 +134,7 @@ class LSTM:
         self.bias = torch.from_numpy(cfg["bias"]).to(device)
         self.Hs = cfg["w_hh"].shape[1]
         self.s_x = None
+        self.fused_step = fused_step
 
     def forward(self, x):
         bits = self.bits
@@ -152,12 +153,26 @@ class LSTM:
         s_ih = _f(self.s_x) * _f(self.s_wih)
         s_hh = _f(s_h) * _f(self.s_whh)
         B.adapt_quantize_f32(h, s_h, bits, out=qh)
+        qh2 = torch.empty_like(qh)
+        acc_last = None
         for t in range(T):
-            B.adapt_approx_linear_packed(self.p_whh, qh, out=acc_hh)
             h = hs[t]
+            if self.fused_step:
+                # product, cell and the next step's quantised h in one kernel; shapes it does not cover are refused
+                # with UNSUPPORTED and take the two calls below
+                try:
+                    B.adapt_lstm_step_f32(self.p_whh, qh, acc_ih[t], s_ih, s_hh, s_h, self.bias, c, h, qh2)
+                    qh, qh2 = qh2, qh
+                    continue
+                except B.AdaptError as e:
+                    if e.code != -2:
+                        raise
+                    self.fused_step = False
+            B.adapt_approx_linear_packed(self.p_whh, qh, out=acc_hh)
+            acc_last = acc_hh
             # the cell also writes the quantised h that the next step multiplies
             B.adapt_lstm_cell_q_f32(acc_ih[t], acc_hh, s_ih, s_hh, self.bias, c, h, qh, s_h, bits)
-        return dict(hs=hs, c=c, acc_ih=acc_ih, acc_hh_last=acc_hh, s_x=self.s_x, s_h=s_h)
+        return dict(hs=hs, c=c, acc_ih=acc_ih, acc_hh_last=acc_last, s_x=self.s_x, s_h=s_h)
 
 
 class DCGAN:

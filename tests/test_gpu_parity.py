@@ -370,10 +370,14 @@ def test_config4_lstm_full_size(B):
     c = wl.config4()
     th = orc.host_threads()
     want = onet.lstm(c, threads=th)
-    got = gnet.LSTM(c).forward(dev(c["x"]))
+    got = gnet.LSTM(c, fused_step=False).forward(dev(c["x"]))        # product and cell as separate calls
     assert np.float32(got["s_x"]) == np.float32(want["s_x"])
     assert (host(got["acc_ih"]) == want["acc_ih"]).all()
     assert (host(got["acc_hh_last"]) == want["acc_hh_last"]).all()
+    net = gnet.LSTM(c)                                                # one kernel per time step
+    one = net.forward(dev(c["x"]))
+    assert net.fused_step, "the benchmark shape must fit the fused kernel"
+    assert bits_equal(host(one["hs"]), want["hs"]) and bits_equal(host(one["c"]), want["c"])
     assert_f32_close(host(got["hs"]), want["hs"])
     assert_f32_close(host(got["c"]), want["c"])
     assert bits_equal(host(got["hs"]), want["hs"])          # the written-out gate functions make this exact
@@ -584,6 +588,44 @@ def test_conv_transpose2d_packed_rect_kernel_and_wide_table(B):
     cnt[0, :] = cnt[-1, :] = cnt[:, 0] = cnt[:, -1] = 2
     cnt[0, 0] = cnt[0, -1] = cnt[-1, 0] = cnt[-1, -1] = 1
     assert (got == (3 * 4 * cnt)[None, None]).all()
+
+
+# ------------------------------------------------------------------ LSTM time step in one kernel
+
+@pytest.mark.parametrize("shape", [(1, 4, 6), (8, 16, 6), (64, 64, 7), (33, 100, 8), (64, 512, 7), (64, 512, 8), (150, 34, 7)])
+def test_lstm_step_fused(B, shape):
+    Bn, Hs, bits = shape
+    rng = np.random.default_rng(sum(shape))
+    lut = wl.make_lut(bits)
+    W = wl.random_i8(rng, (4 * Hs, Hs), bits, "gauss")
+    acc_ih = rng.integers(-40000, 40000, size=(Bn, 4 * Hs)).astype(np.int32)
+    bias = rng.standard_normal(4 * Hs).astype(np.float32)
+    qh = wl.random_i8(rng, (Bn, Hs), bits)
+    c0 = rng.standard_normal((Bn, Hs)).astype(np.float32)
+    Q = (1 << (bits - 1)) - 1
+    s_h = np.float32(1.0) / np.float32(Q)
+    s_ih, s_hh = np.float32(3e-5), np.float32(2e-4)
+    acc_hh = orc.approx_linear(lut, bits, qh, W, threads=4)
+    pw = B.adapt_weights_pack_linear(B.Lut(lut, bits), dev(W))
+    for b in (bias, None):
+        h_w, c_w = orc.lstm_cell(acc_ih, acc_hh, s_ih, s_hh, b, c0)
+        cd = dev(c0)
+        hd = torch.empty((Bn, Hs), dtype=torch.float32, device="cuda")
+        qn = torch.empty((Bn, Hs), dtype=torch.int8, device="cuda")
+        B.adapt_lstm_step_f32(pw, dev(qh), dev(acc_ih), s_ih, s_hh, s_h, dev(b) if b is not None else None, cd, hd, qn)
+        assert bits_equal(host(hd), h_w) and bits_equal(host(cd), c_w)
+        assert (host(qn) == orc.quantize(h_w, s_h, bits)).all()
+
+
+def test_lstm_step_refuses_what_it_does_not_cover(B):
+    L = B.Lut(wl.make_lut(6), 6)
+    pw = B.adapt_weights_pack_linear(L, torch.zeros((4 * 5, 5), dtype=torch.int8, device="cuda"))     # odd Hs
+    z = torch.zeros((3, 20), dtype=torch.int32, device="cuda")
+    c = torch.zeros((3, 5), dtype=torch.float32, device="cuda")
+    q = torch.zeros((3, 5), dtype=torch.int8, device="cuda")
+    with pytest.raises(B.AdaptError) as e:
+        B.adapt_lstm_step_f32(pw, q, z, 1.0, 1.0, 1.0, None, c, c.clone(), q.clone())
+    assert e.value.code == -2
 
 
 # ------------------------------------------------------------------ HIP-graph replay of a network
