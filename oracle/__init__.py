@@ -166,6 +166,57 @@ def dequant(acc, scale, outer, channels, inner, bias=None) -> np.ndarray:
     return y
 
 
+def absmax_rows(x) -> np.ndarray:
+    x = _f32(x)
+    rows = x.shape[0]
+    cols = x.size // rows if rows else 0
+    out = np.empty(rows, dtype=np.float32)
+    _check(lib().orc_absmax_rows_f32(_p(x), ctypes.c_size_t(rows), ctypes.c_size_t(cols), _p(out)), "absmax_rows")
+    return out
+
+
+def quantize_rows(x, scales, bits) -> np.ndarray:
+    x = _f32(x)
+    scales = _f32(scales)
+    rows = x.shape[0]
+    cols = x.size // rows
+    q = np.empty(x.shape, dtype=np.int8)
+    _check(lib().orc_quantize_rows_f32(_p(x), _p(q), ctypes.c_size_t(rows), ctypes.c_size_t(cols), _p(scales), int(bits)),
+           "quantize_rows")
+    return q
+
+
+def dequant_per_channel(acc, scales, outer, channels, inner, bias=None) -> np.ndarray:
+    acc = np.ascontiguousarray(acc)
+    scales = _f32(scales)
+    assert acc.dtype == np.int32 and acc.size == outer * channels * inner and scales.size == channels
+    y = np.empty(acc.shape, dtype=np.float32)
+    b = _f32(bias) if bias is not None else None
+    _check(lib().orc_dequant_i32_per_channel(_p(acc), _p(y), ctypes.c_size_t(outer), ctypes.c_size_t(channels),
+                                             ctypes.c_size_t(inner), _p(scales), _p(b) if b is not None else None),
+           "dequant_per_channel")
+    return y
+
+
+def histogram_abs(x, amax, bins, counts=None) -> np.ndarray:
+    x = _f32(x)
+    if counts is None:
+        counts = np.zeros(bins, dtype=np.uint32)
+    assert counts.dtype == np.uint32 and counts.size == bins
+    _check(lib().orc_histogram_abs_f32(_p(x), ctypes.c_size_t(x.size), ctypes.c_float(float(amax)), int(bins), _p(counts)),
+           "histogram_abs")
+    return counts
+
+
+def percentile_from_histogram(counts, amax, num=999, den=1000) -> np.float32:
+    counts = np.ascontiguousarray(counts, dtype=np.uint32)
+    out = ctypes.c_float(0.0)
+    _check(lib().orc_percentile_from_histogram(_p(counts), int(counts.size), ctypes.c_float(float(amax)),
+                                               ctypes.c_ulonglong(num), ctypes.c_ulonglong(den), ctypes.byref(out)),
+           "percentile_from_histogram")
+    return np.float32(out.value)
+
+
 def relu(x) -> np.ndarray:
     x = _f32(x)
     y = np.empty_like(x)

@@ -259,6 +259,96 @@ int orc_dequant_i32(const int32_t *acc, float *y, size_t outer, size_t channels,
 }
 
 /* ---------------------------------------------------------------------------
+ * The quantiser as the paper uses it (Sec. III-A "Parameter calibration"): weight ranges per output channel,
+ * activation ranges per tensor from a histogram calibrator at a 99.9 % percentile, instead of the plain maximum.
+ * The paper names the method but not the histogram; the reading taken here:
+ *   bins equal-width bins over [0, amax], width = amax / bins (one fp32 division);
+ *   bin(v) = min(bins - 1, (long) trunc(|v| / width)) (one fp32 division); NaN is not counted;
+ *   calib_max = upper edge of the first bin at which the cumulative count reaches ceil(num / den * total),
+ *             = (float)(k + 1) * width (one fp32 multiplication);  then scale = calib_max / Q as before, and
+ *   the quantiser's clamp saturates what lies beyond calib_max.
+ * ------------------------------------------------------------------------- */
+
+/* amax[r] = max |x[r][c]| over the cols of row r (weights [Cout][Cin*kh*kw]: one row per output channel) */
+int orc_absmax_rows_f32(const float *x, size_t rows, size_t cols, float *amax) {
+    if ((!x && rows && cols) || (!amax && rows)) return ORC_BAD_ARG;
+    for (size_t r = 0; r < rows; ++r) {
+        float m = 0.0f;
+        for (size_t c = 0; c < cols; ++c) {
+            const float a = fabsf(x[r * cols + c]);
+            if (a > m) m = a;
+        }
+        amax[r] = m;
+    }
+    return ORC_OK;
+}
+
+/* q[r][c] = clamp(round_half_even(x[r][c] / scale[r]), -Q, Q): the quantiser above with one scale per row */
+int orc_quantize_rows_f32(const float *x, int8_t *q, size_t rows, size_t cols, const float *scale, int bits) {
+    if (!x || !q || !scale || bits < 2 || bits > 8) return ORC_BAD_ARG;
+    const float Q = (float)((1 << (bits - 1)) - 1);
+    for (size_t r = 0; r < rows; ++r) {
+        if (!(scale[r] > 0.0f)) return ORC_BAD_ARG;
+        for (size_t c = 0; c < cols; ++c) {
+            float v = rintf(x[r * cols + c] / scale[r]);
+            if (v != v) v = 0.0f;
+            if (v > Q) v = Q;
+            if (v < -Q) v = -Q;
+            q[r * cols + c] = (int8_t)v;
+        }
+    }
+    return ORC_OK;
+}
+
+/* y = float(acc) * scale[c] (+ bias[c]): the dequantiser with one scale per output channel (= s_x * s_w[c]) */
+int orc_dequant_i32_per_channel(const int32_t *acc, float *y, size_t outer, size_t channels, size_t inner,
+                                const float *scale, const float *bias) {
+    if (!acc || !y || !scale) return ORC_BAD_ARG;
+    for (size_t o = 0; o < outer; ++o)
+        for (size_t c = 0; c < channels; ++c)
+            for (size_t i = 0; i < inner; ++i) {
+                const size_t idx = (o * channels + c) * inner + i;
+                float v = (float)acc[idx] * scale[c];
+                if (bias) v = v + bias[c];
+                y[idx] = v;
+            }
+    return ORC_OK;
+}
+
+/* counts[bin(x_i)] += 1 for every i (counts is accumulated into, so several batches can share it) */
+int orc_histogram_abs_f32(const float *x, size_t n, float amax, int bins, uint32_t *counts) {
+    if ((!x && n) || !counts || bins < 1 || !(amax > 0.0f)) return ORC_BAD_ARG;
+    const float width = amax / (float)bins;
+    for (size_t i = 0; i < n; ++i) {
+        const float a = fabsf(x[i]);
+        if (a != a) continue;
+        const float t = a / width;
+        long b = t >= (float)bins ? (long)bins - 1 : (long)t;
+        if (b > bins - 1) b = bins - 1;
+        counts[b] += 1u;
+    }
+    return ORC_OK;
+}
+
+/* calib_max for the fraction num / den of the counted values (e.g. 999 / 1000) */
+int orc_percentile_from_histogram(const uint32_t *counts, int bins, float amax, unsigned long long num,
+                                  unsigned long long den, float *calib_max) {
+    if (!counts || !calib_max || bins < 1 || !(amax > 0.0f) || den == 0 || num > den) return ORC_BAD_ARG;
+    unsigned long long total = 0;
+    for (int b = 0; b < bins; ++b) total += counts[b];
+    const unsigned long long target = (total * num + den - 1) / den;     /* ceil(total * num / den) */
+    const float width = amax / (float)bins;
+    unsigned long long cum = 0;
+    int k = bins - 1;
+    for (int b = 0; b < bins; ++b) {
+        cum += counts[b];
+        if (cum >= target) { k = b; break; }
+    }
+    *calib_max = (float)(k + 1) * width;
+    return ORC_OK;
+}
+
+/* ---------------------------------------------------------------------------
  * fp32 glue between approximate layers.  Each is one IEEE operation per element
  * in the stated order, so that the integers produced by the next quantiser are
  * reproducible.

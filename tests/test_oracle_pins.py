@@ -416,3 +416,75 @@ def test_network_runners_track_fp32_networks_with_exact_table():
     ref = x.numpy()
     assert og["out"].shape == (2, 3, 64, 64)
     assert np.linalg.norm(og["out"] - ref) / np.linalg.norm(ref) < 0.08
+
+
+# ------------------------------------------------------------------ per-channel ranges and the percentile calibrator
+# (Sec. III-A "Parameter calibration": weight ranges per channel, activation range from a 99.9 % histogram percentile)
+
+def test_per_channel_quantiser_is_the_per_tensor_one_row_by_row():
+    rng = np.random.default_rng(11)
+    w = (rng.standard_normal((7, 5, 3, 3)) * rng.uniform(0.01, 3.0, size=(7, 1, 1, 1))).astype(np.float32)
+    amax = orc.absmax_rows(w)
+    assert np.array_equal(amax, np.abs(w).reshape(7, -1).max(axis=1))            # library routine, exact
+    scales = np.array([orc.scale_from_amax(a, 6) for a in amax], dtype=np.float32)
+    q = orc.quantize_rows(w, scales, 6)
+    for r in range(7):
+        assert np.array_equal(q[r], orc.quantize(w[r], scales[r], 6))
+        assert np.abs(q[r]).max() == 31                                             # every channel uses its full range
+    # an all-zero row keeps scale 1 and quantises to zeros
+    w[3] = 0
+    s3 = orc.scale_from_amax(orc.absmax_rows(w)[3], 6)
+    assert s3 == 1.0 and not orc.quantize_rows(w, np.where(np.arange(7) == 3, s3, scales).astype(np.float32), 6)[3].any()
+
+
+def test_per_channel_dequant_is_one_rounded_product_per_element():
+    rng = np.random.default_rng(12)
+    acc = rng.integers(-2**31, 2**31 - 1, size=(3, 5, 4), dtype=np.int64).astype(np.int32)
+    s = rng.uniform(1e-6, 1e-2, size=5).astype(np.float32)
+    b = rng.standard_normal(5).astype(np.float32)
+    want = acc.astype(np.float32) * s[None, :, None]                               # numpy fp32: one IEEE product
+    assert np.array_equal(orc.dequant_per_channel(acc, s, 3, 5, 4).view(np.uint32), want.view(np.uint32))
+    want_b = want + b[None, :, None]
+    assert np.array_equal(orc.dequant_per_channel(acc, s, 3, 5, 4, b).view(np.uint32), want_b.view(np.uint32))
+    # with equal scales it is the per-tensor dequantiser
+    s1 = np.full(5, s[0], dtype=np.float32)
+    assert np.array_equal(orc.dequant_per_channel(acc, s1, 3, 5, 4, b), orc.dequant(acc, s[0], 3, 5, 4, b))
+
+
+def test_histogram_counts_and_edges():
+    bins, amax = 8, np.float32(4.0)                 # width 0.5, exactly representable
+    x = np.array([0.0, 0.25, -0.25, 0.5, 0.74, -1.0, 3.99, 4.0, -4.0, np.nan, 2.5], dtype=np.float32)
+    h = orc.histogram_abs(x, amax, bins)
+    assert h.tolist() == [3, 2, 1, 0, 0, 1, 0, 3]    # 0.5 opens bin 1; |x| = amax falls into the last bin; NaN is not counted
+    # accumulation over batches, and agreement with numpy on values away from bin edges
+    rng = np.random.default_rng(13)
+    y = (rng.integers(0, 8, size=1000) + rng.uniform(0.1, 0.9, size=1000)).astype(np.float32) * np.float32(0.5)
+    y *= rng.choice([-1.0, 1.0], size=1000).astype(np.float32)
+    h2 = orc.histogram_abs(y, amax, bins, h.copy())
+    assert (h2 - h).tolist() == np.histogram(np.abs(y), bins=bins, range=(0.0, 4.0))[0].tolist()
+    assert int(h2.sum()) == 10 + 1000
+
+
+def test_percentile_closed_forms_and_bracketing():
+    # 1000 values 0.5, 1.5, ..., 999.5 (one per unit bin when bins = 1000 and amax = 1000):
+    x = (np.arange(1000) + 0.5).astype(np.float32)
+    h = orc.histogram_abs(x, 1000.0, 1000)
+    assert h.tolist() == [1] * 1000
+    assert orc.percentile_from_histogram(h, 1000.0, 999, 1000) == np.float32(999.0)     # 999 of 1000 values lie below 999
+    assert orc.percentile_from_histogram(h, 1000.0, 1, 2) == np.float32(500.0)
+    assert orc.percentile_from_histogram(h, 1000.0, 1000, 1000) == np.float32(1000.0)   # the plain maximum
+    assert orc.percentile_from_histogram(h, 1000.0, 0, 1000) == np.float32(1.0)         # first bin edge
+    # random heavy-tailed data: calib_max brackets the requested fraction to within one bin
+    rng = np.random.default_rng(14)
+    v = (rng.standard_normal(50_000) ** 3).astype(np.float32)
+    amax = orc.absmax(v)
+    bins = 2048
+    c = orc.percentile_from_histogram(orc.histogram_abs(v, amax, bins), amax, 999, 1000)
+    width = np.float32(amax) / np.float32(bins)
+    a = np.abs(v)
+    assert np.count_nonzero(a < c) >= math.ceil(0.999 * v.size) - 1
+    assert np.count_nonzero(a < c - np.float32(1.001) * width) < math.ceil(0.999 * v.size)
+    assert c < amax                                   # the tail beyond it will saturate in the quantiser
+    s = orc.scale_from_amax(c, 8)
+    q = orc.quantize(v, s, 8)
+    assert np.abs(q).max() == 127 and 0 < np.count_nonzero(np.abs(q) == 127) <= 0.002 * v.size + 2
