@@ -92,6 +92,28 @@ int adapt_quantize_f32(const float *x_dev, int8_t *q_dev, size_t n, float scale,
 int adapt_dequant_i32(const int32_t *acc_dev, float *y_dev, size_t outer, size_t channels, size_t inner,
                       float scale, const float *bias_dev, void *stream);
 
+/* The quantiser as the paper configures it (Sec. III-A "Parameter calibration": weight ranges per output channel,
+ * activation range calib_max from a histogram calibrator at a 99.9 % percentile; scale = range / Q as above).
+ * The paper names the method, not the histogram; this library's definition: `bins` equal-width bins over [0, amax],
+ * width = amax / bins, bin(v) = min(bins - 1, trunc(|v| / width)) (IEEE fp32 divisions), NaN not counted;
+ * calib_max = (k + 1) * width for the first bin k whose cumulative count reaches ceil(total * num / den).
+ * Values beyond calib_max saturate in the quantiser's clamp. */
+
+/* amax_dev[r] = max |x[r][0..cols)| for rows of a dense [rows][cols] matrix (weights: one row per output channel) */
+int adapt_absmax_rows_f32(const float *x_dev, size_t rows, size_t cols, float *amax_dev, void *stream);
+/* q[r][c] = quantise(x[r][c], scales_dev[r], bits) as adapt_quantize_f32; every scale must be > 0 */
+int adapt_quantize_rows_f32(const float *x_dev, int8_t *q_dev, size_t rows, size_t cols, const float *scales_dev, int bits,
+                            void *stream);
+/* adapt_dequant_i32 with one scale per channel: y = float(acc) * scales_dev[c] (+ bias[c]); scales_dev[c] = s_x * s_w[c] */
+int adapt_dequant_i32_per_channel(const int32_t *acc_dev, float *y_dev, size_t outer, size_t channels, size_t inner,
+                                  const float *scales_dev, const float *bias_dev, void *stream);
+/* counts_dev[bin(x_i)] += 1 for i < n (uint32 [bins], 1 <= bins <= 4096; accumulated into, so the caller zeroes it
+ * first and may add several batches); amax > 0 is the range (e.g. from adapt_absmax_f32) */
+int adapt_histogram_abs_f32(const float *x_dev, size_t n, float amax, int bins, uint32_t *counts_dev, void *stream);
+/* calib_max_dev[0] for the fraction num / den (99.9 %: 999 / 1000; den <= 2^20) of the counted values */
+int adapt_percentile_from_histogram(const uint32_t *counts_dev, int bins, float amax, unsigned num, unsigned den,
+                                    float *calib_max_dev, void *stream);
+
 /* ------------------------------------------------------------------------------------------------
  * Approximate layers (Sec. III-B, IV): every inner-product term is one table entry.
  * ---------------------------------------------------------------------------------------------- */
@@ -166,15 +188,17 @@ int adapt_approx_conv_transpose2d_packed(const adapt_weights *w, const int8_t *x
  * rescaling inside the product kernel, so a layer is two launches instead of four or five and the int8 / int32
  * intermediates never reach memory.  y_dev has the shape of the int32 output of the corresponding *_packed call
  * and also serves as scratch for the sums where they cannot be rescaled in the product kernel.  s_out = s_x * s_w,
- * formed in fp32 by the caller; bias_dev [channels] or NULL.
+ * formed in fp32 by the caller; with per-channel weight ranges s_out_vec_dev [channels] holds s_x * s_w[c] instead
+ * (then s_out is ignored; NULL otherwise); bias_dev [channels] or NULL.
  * ---------------------------------------------------------------------------------------------- */
 int adapt_linear_layer_f32(const adapt_weights *w, const float *x_dev, float *y_dev, int M, float s_x, float s_out,
-                           const float *bias_dev, int act, void *stream);
+                           const float *s_out_vec_dev, const float *bias_dev, int act, void *stream);
 int adapt_conv2d_layer_f32(const adapt_weights *w, const float *x_dev, float *y_dev, int N, int H, int W, int stride_h,
                            int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, float s_x, float s_out,
-                           const float *bias_dev, int act, void *stream);
+                           const float *s_out_vec_dev, const float *bias_dev, int act, void *stream);
 int adapt_conv_transpose2d_layer_f32(const adapt_weights *w, const float *x_dev, float *y_dev, int N, int H, int W, int pad,
-                                     float s_x, float s_out, const float *bias_dev, int act, void *stream);
+                                     float s_x, float s_out, const float *s_out_vec_dev, const float *bias_dev, int act,
+                                     void *stream);
 
 /* ------------------------------------------------------------------------------------------------
  * fp32 operations between approximate layers.  Each element is produced by single IEEE fp32

@@ -23,6 +23,8 @@ EXPORTS = [
     "adapt_last_error", "adapt_device_cu_count",
     "adapt_lut_create", "adapt_lut_destroy", "adapt_lut_info",
     "adapt_absmax_f32", "adapt_quantize_f32", "adapt_dequant_i32",
+    "adapt_absmax_rows_f32", "adapt_quantize_rows_f32", "adapt_dequant_i32_per_channel",
+    "adapt_histogram_abs_f32", "adapt_percentile_from_histogram",
     "adapt_approx_linear", "adapt_approx_conv2d", "adapt_approx_conv_transpose2d",
     "adapt_weights_pack_linear", "adapt_weights_pack_conv2d", "adapt_weights_pack_conv_transpose2d",
     "adapt_weights_destroy",
@@ -60,6 +62,11 @@ def load() -> ctypes.CDLL:
     L.adapt_lut_info.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_int32),
                                  ctypes.POINTER(ctypes.c_int32)]
     L.adapt_absmax_f32.argtypes = [vp, sz, vp, vp]
+    L.adapt_absmax_rows_f32.argtypes = [vp, sz, sz, vp, vp]
+    L.adapt_quantize_rows_f32.argtypes = [vp, vp, sz, sz, vp, i32, vp]
+    L.adapt_dequant_i32_per_channel.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp]
+    L.adapt_histogram_abs_f32.argtypes = [vp, sz, f32, i32, vp, vp]
+    L.adapt_percentile_from_histogram.argtypes = [vp, i32, f32, ctypes.c_uint, ctypes.c_uint, vp, vp]
     L.adapt_quantize_f32.argtypes = [vp, vp, sz, f32, i32, vp]
     L.adapt_dequant_i32.argtypes = [vp, vp, sz, sz, sz, f32, vp, vp]
     L.adapt_approx_linear.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
@@ -70,9 +77,9 @@ def load() -> ctypes.CDLL:
     L.adapt_weights_pack_conv_transpose2d.argtypes = [ctypes.POINTER(vp), vp, vp, i32, i32, i32, i32, i32, vp]
     L.adapt_approx_conv_transpose2d_packed.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
     L.adapt_weights_destroy.argtypes = [vp]
-    L.adapt_linear_layer_f32.argtypes = [vp, vp, vp, i32, f32, f32, vp, i32, vp]
-    L.adapt_conv2d_layer_f32.argtypes = [vp, vp, vp] + [i32] * 9 + [f32, f32, vp, i32, vp]
-    L.adapt_conv_transpose2d_layer_f32.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, f32, vp, i32, vp]
+    L.adapt_linear_layer_f32.argtypes = [vp, vp, vp, i32, f32, f32, vp, vp, i32, vp]
+    L.adapt_conv2d_layer_f32.argtypes = [vp, vp, vp] + [i32] * 9 + [f32, f32, vp, vp, i32, vp]
+    L.adapt_conv_transpose2d_layer_f32.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, f32, vp, vp, i32, vp]
     L.adapt_approx_linear_packed.argtypes = [vp, vp, vp, i32, vp]
     L.adapt_approx_conv2d_packed.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
     L.adapt_relu_f32.argtypes = [vp, vp, sz, vp]
@@ -375,13 +382,21 @@ def adapt_lstm_cell_q_f32(acc_ih, acc_hh, s_ih: float, s_hh: float, bias, c, h, 
 ACT_NONE, ACT_RELU, ACT_TANH = 0, 1, 2
 
 
+def _scales(s_out):
+    """(scalar, vector) forms of an output scale: a tensor means one scale per channel."""
+    if isinstance(s_out, torch.Tensor):
+        return 1.0, _ptr(s_out, torch.float32)
+    return float(s_out), None
+
+
 def adapt_linear_layer_f32(pw: PackedWeights, x, s_x, s_out, bias=None, act=ACT_NONE, out=None, stream=None):
     M, K = x.shape
     N, K2 = pw.shape
     assert K == K2 and pw.kind == "linear"
     if out is None:
         out = torch.empty((M, N), dtype=torch.float32, device=x.device)
-    _chk(load().adapt_linear_layer_f32(pw.handle, _ptr(x, torch.float32), _ptr(out, torch.float32), M, float(s_x), float(s_out),
+    sc, sv = _scales(s_out)
+    _chk(load().adapt_linear_layer_f32(pw.handle, _ptr(x, torch.float32), _ptr(out, torch.float32), M, float(s_x), sc, sv,
                                        _ptr(bias, torch.float32), act, _stream(stream)))
     return out
 
@@ -394,8 +409,9 @@ def adapt_conv2d_layer_f32(pw: PackedWeights, x, s_x, s_out, stride=(1, 1), pad=
     if out is None:
         Ho, Wo = conv_out_hw(H, W, kh, kw, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1])
         out = torch.empty((N, Cout, Ho, Wo), dtype=torch.float32, device=x.device)
+    sc, sv = _scales(s_out)
     _chk(load().adapt_conv2d_layer_f32(pw.handle, _ptr(x, torch.float32), _ptr(out, torch.float32), N, H, W, stride[0], stride[1],
-                                       pad[0], pad[1], dil[0], dil[1], float(s_x), float(s_out), _ptr(bias, torch.float32), act,
+                                       pad[0], pad[1], dil[0], dil[1], float(s_x), sc, sv, _ptr(bias, torch.float32), act,
                                        _stream(stream)))
     return out
 
@@ -407,8 +423,9 @@ def adapt_conv_transpose2d_layer_f32(pw: PackedWeights, x, s_x, s_out, pad=0, bi
     if out is None:
         Ho, Wo = (H - 1) * pw.stride - 2 * pad + kh, (W - 1) * pw.stride - 2 * pad + kw
         out = torch.empty((N, Cout, Ho, Wo), dtype=torch.float32, device=x.device)
+    sc, sv = _scales(s_out)
     _chk(load().adapt_conv_transpose2d_layer_f32(pw.handle, _ptr(x, torch.float32), _ptr(out, torch.float32), N, H, W, pad,
-                                                 float(s_x), float(s_out), _ptr(bias, torch.float32), act, _stream(stream)))
+                                                 float(s_x), sc, sv, _ptr(bias, torch.float32), act, _stream(stream)))
     return out
 
 
@@ -420,3 +437,47 @@ def adapt_lstm_step_f32(pw_hh: PackedWeights, qh, acc_ih, s_ih, s_hh, s_h, bias,
                                     float(s_h), _ptr(bias, torch.float32), _ptr(c, torch.float32), _ptr(h, torch.float32),
                                     _ptr(qh_next, torch.int8), B, Hs, _stream(stream)))
     return h, c, qh_next
+
+
+def adapt_absmax_rows_f32(x, out=None, stream=None):
+    rows = x.shape[0]
+    cols = x.numel() // rows if rows else 0
+    if out is None:
+        out = torch.empty((rows,), dtype=torch.float32, device=x.device)
+    _chk(load().adapt_absmax_rows_f32(_ptr(x, torch.float32), rows, cols, _ptr(out, torch.float32), _stream(stream)))
+    return out
+
+
+def adapt_quantize_rows_f32(x, scales, bits, out=None, stream=None):
+    rows = x.shape[0]
+    cols = x.numel() // rows
+    if out is None:
+        out = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    _chk(load().adapt_quantize_rows_f32(_ptr(x, torch.float32), _ptr(out, torch.int8), rows, cols, _ptr(scales, torch.float32),
+                                        bits, _stream(stream)))
+    return out
+
+
+def adapt_dequant_i32_per_channel(acc, scales, outer, channels, inner, bias=None, out=None, stream=None):
+    if out is None:
+        out = torch.empty(acc.shape, dtype=torch.float32, device=acc.device)
+    _chk(load().adapt_dequant_i32_per_channel(_ptr(acc, torch.int32), _ptr(out, torch.float32), outer, channels, inner,
+                                              _ptr(scales, torch.float32), _ptr(bias, torch.float32), _stream(stream)))
+    return out
+
+
+def adapt_histogram_abs_f32(x, amax, bins, counts=None, stream=None):
+    """counts (int32 tensor holding uint32 counters) is accumulated into; a new one starts at zero."""
+    if counts is None:
+        counts = torch.zeros((bins,), dtype=torch.int32, device=x.device)
+    _chk(load().adapt_histogram_abs_f32(_ptr(x, torch.float32), x.numel(), float(amax), bins, _ptr(counts, torch.int32),
+                                        _stream(stream)))
+    return counts
+
+
+def adapt_percentile_from_histogram(counts, amax, num=999, den=1000, out=None, stream=None):
+    if out is None:
+        out = torch.empty((1,), dtype=torch.float32, device=counts.device)
+    _chk(load().adapt_percentile_from_histogram(_ptr(counts, torch.int32), counts.numel(), float(amax), num, den,
+                                                _ptr(out, torch.float32), _stream(stream)))
+    return out

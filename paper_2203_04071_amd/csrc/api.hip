@@ -81,13 +81,14 @@ struct LayerIO {
     int deq = 0;                    // the output buffer receives fp32 y = float(acc) * s_out (+ bias[c]) (act 1: ReLU, 2: tanh)
     int act = 0;
     float s_out = 1.0f;
+    const float *s_out_vec = nullptr;   // one output scale per channel instead of s_out
     const float *bias = nullptr;
     // rescaling inside the product kernel needs a single table pass and an activation it knows
     bool fused(int storage) const { return deq && storage == 0 && act <= 1; }
 };
 
 int finish_inplace(int32_t *buf, size_t n, size_t channels, size_t inner, const LayerIO &io, hipStream_t s) {
-    adapt::finish_inplace_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, s>>>(buf, n, channels, inner, io.s_out, io.bias, io.act);
+    adapt::finish_inplace_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, s>>>(buf, n, channels, inner, io.s_out, io.s_out_vec, io.bias, io.act);
     HIP_TRY(hipGetLastError());
     return ADAPT_OK;
 }
@@ -353,6 +354,7 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     p.MT = MT; p.KS = KS;
     const bool fuse = io && io->fused(lut->storage);
     p.deq = fuse ? 1 : 0; p.act = fuse ? io->act : 0; p.scale = fuse ? io->s_out : 1.0f; p.bias = fuse ? io->bias : nullptr;
+    p.scales = fuse ? io->s_out_vec : nullptr;
     p.lstm = lstm ? 1 : 0; p.Hs = 0; p.acc_ih = nullptr; p.c = p.h = nullptr; p.qh_next = nullptr;
     p.s_ih = p.s_hh = p.s_h = p.Qh = 1.0f;
     if (lstm) {
@@ -564,6 +566,7 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     const bool fuse_in_kernel = fuse && !split;
     p.deq = fuse_in_kernel ? 1 : 0; p.act = fuse_in_kernel ? io->act : 0;
     p.scale = fuse_in_kernel ? io->s_out : 1.0f; p.bias = fuse_in_kernel ? io->bias : nullptr;
+    p.scales = fuse_in_kernel ? io->s_out_vec : nullptr;
     // one base offset per lane is enough when the R rows of a lane are equally spaced in xt
     const bool regular = (c.M % R == 0) && (c.HoWo == 1 || c.Wo % R == 0);
     const bool xmajor = c.xmajor && R == 8 && c.M % 8 == 0 && c.Wo % 4 == 0;
@@ -593,7 +596,7 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
         if (split && rc == ADAPT_OK) {
             adapt::reduce_partials_kernel<<<ew_grid(c.out_elems), adapt::EW_THREADS, 0, s>>>(
                 c.partial, pl.ksplit, c.out_elems, out, c.out_elems, half == 0 ? -1 : 16, (fuse && half == 0) ? 1 : 0, c.out_channels,
-                c.out_inner, fuse ? io->s_out : 1.0f, fuse ? io->bias : nullptr, fuse ? io->act : 0);
+                c.out_inner, fuse ? io->s_out : 1.0f, fuse ? io->s_out_vec : nullptr, fuse ? io->bias : nullptr, fuse ? io->act : 0);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) rc = fail(ADAPT_ERR_HIP, "reduce_partials launch: %s", hipGetErrorString(e));
         }
@@ -1220,15 +1223,70 @@ int adapt_approx_conv2d_packed(const adapt_weights *h, const int8_t *x_dev, int3
                         pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream, &h->ws, nullptr, h);
 }
 
+/* ------------------------------------------------------------------ per-channel ranges, percentile calibrator */
+
+int adapt_absmax_rows_f32(const float *x_dev, size_t rows, size_t cols, float *amax_dev, void *stream) {
+    if (rows == 0) return ADAPT_OK;
+    if (!amax_dev || (!x_dev && cols)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_absmax_rows_f32: NULL pointer");
+    if (rows > 0x7fffffffULL) return fail(ADAPT_ERR_UNSUPPORTED, "adapt_absmax_rows_f32: more than 2^31-1 rows");
+    adapt::absmax_rows_kernel<<<(unsigned)rows, adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, cols, amax_dev);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+int adapt_quantize_rows_f32(const float *x_dev, int8_t *q_dev, size_t rows, size_t cols, const float *scales_dev, int bits,
+                            void *stream) {
+    if (bits < 2 || bits > 8) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_quantize_rows_f32: bits=%d not in [2,8]", bits);
+    if (rows == 0 || cols == 0) return ADAPT_OK;
+    if (!x_dev || !q_dev || !scales_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_quantize_rows_f32: NULL pointer");
+    adapt::quantize_rows_kernel<<<ew_grid(rows * cols), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(
+        x_dev, q_dev, rows, cols, scales_dev, (float)((1 << (bits - 1)) - 1));
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+int adapt_dequant_i32_per_channel(const int32_t *acc_dev, float *y_dev, size_t outer, size_t channels, size_t inner,
+                                  const float *scales_dev, const float *bias_dev, void *stream) {
+    const size_t n = outer * channels * inner;
+    if (n == 0) return ADAPT_OK;
+    if (!acc_dev || !y_dev || !scales_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_dequant_i32_per_channel: NULL pointer");
+    adapt::dequant_pc_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(acc_dev, y_dev, n, channels, inner, scales_dev,
+                                                                                        bias_dev);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+int adapt_histogram_abs_f32(const float *x_dev, size_t n, float amax, int bins, uint32_t *counts_dev, void *stream) {
+    if (bins < 1 || bins > 4096) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_histogram_abs_f32: bins=%d not in [1,4096]", bins);
+    if (!(amax > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_histogram_abs_f32: amax must be > 0");
+    if (!counts_dev || (!x_dev && n)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_histogram_abs_f32: NULL pointer");
+    if (n == 0) return ADAPT_OK;
+    const float width = amax / (float)bins;
+    adapt::histogram_abs_kernel<<<ew_grid(n / 8 + 1), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, n, width, bins, counts_dev);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+int adapt_percentile_from_histogram(const uint32_t *counts_dev, int bins, float amax, unsigned num, unsigned den, float *calib_max_dev,
+                                    void *stream) {
+    if (bins < 1 || bins > 4096) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_percentile_from_histogram: bins=%d not in [1,4096]", bins);
+    if (!(amax > 0.0f) || den == 0 || num > den || den > (1u << 20))
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_percentile_from_histogram: need amax > 0 and 0 <= num <= den <= 2^20");
+    if (!counts_dev || !calib_max_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_percentile_from_histogram: NULL pointer");
+    adapt::percentile_kernel<<<1, 64, 0, (hipStream_t)stream>>>(counts_dev, bins, amax / (float)bins, num, den, calib_max_dev);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
 /* ------------------------------------------------------------------ whole layers, fp32 in and out */
 
 static int layer_io(LayerIO *io, const adapt_weights *h, const float *x_dev, const float *y_dev, float s_x, float s_out,
-                    const float *bias_dev, int act, const char *who) {
+                    const float *s_out_vec_dev, const float *bias_dev, int act, const char *who) {
     if (!x_dev || !y_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
     if (!(s_x > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: s_x must be > 0", who);
     if (act < 0 || act > 2) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: act=%d not in {0, 1, 2}", who, act);
     io->xf = x_dev; io->s_x = s_x; io->Q = (float)((1 << (h->bits - 1)) - 1);
-    io->deq = 1; io->act = act; io->s_out = s_out; io->bias = bias_dev;
+    io->deq = 1; io->act = act; io->s_out = s_out; io->s_out_vec = s_out_vec_dev; io->bias = bias_dev;
     return ADAPT_OK;
 }
 
@@ -1243,14 +1301,14 @@ static int quantize_into_ws(const adapt_weights *h, const LayerIO &io, size_t n,
 }
 
 int adapt_linear_layer_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int M, float s_x, float s_out,
-                           const float *bias_dev, int act, void *stream) {
+                           const float *s_out_vec_dev, const float *bias_dev, int act, void *stream) {
     const char *who = "adapt_linear_layer_f32";
     int rc = check_weights(h, 0, who);
     if (rc) return rc;
     if (M < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: negative M", who);
     if (M == 0) return ADAPT_OK;
     LayerIO io;
-    if ((rc = layer_io(&io, h, x_dev, y_dev, s_x, s_out, bias_dev, act, who))) return rc;
+    if ((rc = layer_io(&io, h, x_dev, y_dev, s_x, s_out, s_out_vec_dev, bias_dev, act, who))) return rc;
     if ((long long)M * h->Cp >= 0x7fffff00LL || (long long)M * h->N > 0x7fffffffLL)
         return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
     hipStream_t s = (hipStream_t)stream;
@@ -1268,8 +1326,8 @@ int adapt_linear_layer_f32(const adapt_weights *h, const float *x_dev, float *y_
 }
 
 int adapt_conv2d_layer_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W, int stride_h, int stride_w,
-                           int pad_h, int pad_w, int dil_h, int dil_w, float s_x, float s_out, const float *bias_dev, int act,
-                           void *stream) {
+                           int pad_h, int pad_w, int dil_h, int dil_w, float s_x, float s_out, const float *s_out_vec_dev,
+                           const float *bias_dev, int act, void *stream) {
     const char *who = "adapt_conv2d_layer_f32";
     int rc = check_weights(h, 1, who);
     if (rc) return rc;
@@ -1281,7 +1339,7 @@ int adapt_conv2d_layer_f32(const adapt_weights *h, const float *x_dev, float *y_
     const long long Ho = eh / stride_h + 1, Wo = ew / stride_w + 1;
     if (N == 0) return ADAPT_OK;
     LayerIO io;
-    if ((rc = layer_io(&io, h, x_dev, y_dev, s_x, s_out, bias_dev, act, who))) return rc;
+    if ((rc = layer_io(&io, h, x_dev, y_dev, s_x, s_out, s_out_vec_dev, bias_dev, act, who))) return rc;
     const long long xt_bytes = (long long)N * (H + 2LL * pad_h) * (W + 2LL * pad_w) * h->Cp;
     if (xt_bytes >= 0x7fffff00LL || (long long)N * h->N * Ho * Wo > 0x7fffffffLL || (long long)N * Ho * Wo > 0x7fffffffLL)
         return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
@@ -1290,7 +1348,7 @@ int adapt_conv2d_layer_f32(const adapt_weights *h, const float *x_dev, float *y_
 }
 
 int adapt_conv_transpose2d_layer_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W, int pad, float s_x,
-                                     float s_out, const float *bias_dev, int act, void *stream) {
+                                     float s_out, const float *s_out_vec_dev, const float *bias_dev, int act, void *stream) {
     const char *who = "adapt_conv_transpose2d_layer_f32";
     int rc = check_weights(h, 2, who);
     if (rc) return rc;
@@ -1299,7 +1357,7 @@ int adapt_conv_transpose2d_layer_f32(const adapt_weights *h, const float *x_dev,
     if (Ho < 1 || Wo < 1) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: empty output", who);
     if (N == 0) return ADAPT_OK;
     LayerIO io;
-    if ((rc = layer_io(&io, h, x_dev, y_dev, s_x, s_out, bias_dev, act, who))) return rc;
+    if ((rc = layer_io(&io, h, x_dev, y_dev, s_x, s_out, s_out_vec_dev, bias_dev, act, who))) return rc;
     if ((long long)N * h->N * Ho * Wo > 0x7fffffffLL || (long long)N * h->Cin * H * W > 0x7fffffffLL)
         return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
     hipStream_t s = (hipStream_t)stream;

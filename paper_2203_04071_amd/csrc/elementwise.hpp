@@ -73,6 +73,90 @@ __global__ __launch_bounds__(EW_THREADS) void quantize_kernel(const float *__res
         q[i] = (int8_t)quant1(x[i], scale, Q);
 }
 
+// ---- the quantiser as the paper configures it (Sec. III-A "Parameter calibration"): weight ranges per output
+// channel, activation range from a histogram percentile
+
+// amax[r] = max |x[r][0..cols)|; one workgroup per row
+__global__ __launch_bounds__(EW_THREADS) void absmax_rows_kernel(const float *__restrict__ x, size_t cols, float *__restrict__ amax) {
+    __shared__ float part[EW_THREADS / 64];
+    const float *row = x + (size_t)blockIdx.x * cols;
+    float m = 0.0f;
+    for (size_t c = threadIdx.x; c < cols; c += EW_THREADS) {
+        const float a = fabsf(row[c]);
+        if (a > m) m = a;          // NaN compares false and is skipped
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const float o = __shfl_xor(m, off, 64);
+        if (o > m) m = o;
+    }
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < EW_THREADS / 64; ++w)
+            if (part[w] > m) m = part[w];
+        amax[blockIdx.x] = m;
+    }
+}
+
+// q[r][c] = quantise(x[r][c], scale[r])
+__global__ __launch_bounds__(EW_THREADS) void quantize_rows_kernel(const float *__restrict__ x, int8_t *__restrict__ q, size_t rows,
+                                                                   size_t cols, const float *__restrict__ scale, float Q) {
+    const size_t n = rows * cols;
+    const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) q[i] = (int8_t)quant1(x[i], scale[i / cols], Q);
+}
+
+// y = float(acc) * scale[c] (+ bias[c])
+__global__ __launch_bounds__(EW_THREADS) void dequant_pc_kernel(const int32_t *__restrict__ acc, float *__restrict__ y, size_t n,
+                                                                size_t channels, size_t inner, const float *__restrict__ scale,
+                                                                const float *__restrict__ bias) {
+    const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
+        const size_t c = (i / inner) % channels;
+        float v = (float)acc[i] * scale[c];
+        if (bias) v = v + bias[c];
+        y[i] = v;
+    }
+}
+
+// counts[bin(|x_i|)] += 1 with bins equal bins over [0, amax]: bin(a) = min(bins - 1, trunc(a / width)), width = amax / bins
+// (both IEEE fp32 divisions); NaN is not counted.  Per-workgroup histogram in LDS (bins <= 4096), then one atomic per
+// non-empty bin.
+__global__ __launch_bounds__(EW_THREADS) void histogram_abs_kernel(const float *__restrict__ x, size_t n, float width, int bins,
+                                                                   uint32_t *__restrict__ counts) {
+    __shared__ uint32_t h[4096];
+    for (int b = threadIdx.x; b < bins; b += EW_THREADS) h[b] = 0;
+    __syncthreads();
+    const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
+        const float a = fabsf(x[i]);
+        if (a != a) continue;
+        const float t = a / width;
+        const int b = t >= (float)bins ? bins - 1 : (int)t;
+        atomicAdd(&h[b < bins ? b : bins - 1], 1u);
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < bins; b += EW_THREADS)
+        if (h[b]) atomicAdd(&counts[b], h[b]);
+}
+
+// calib_max = (k + 1) * width for the first bin k at which the cumulative count reaches ceil(total * num / den)
+__global__ void percentile_kernel(const uint32_t *__restrict__ counts, int bins, float width, unsigned long long num,
+                                  unsigned long long den, float *__restrict__ out) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    unsigned long long total = 0;
+    for (int b = 0; b < bins; ++b) total += counts[b];
+    const unsigned long long target = (total * num + den - 1) / den;
+    unsigned long long cum = 0;
+    int k = bins - 1;
+    for (int b = 0; b < bins; ++b) {
+        cum += counts[b];
+        if (cum >= target) { k = b; break; }
+    }
+    out[0] = (float)(k + 1) * width;
+}
+
 // y = float(acc) * scale (+ bias[c]); channel of flat index i is (i / inner) % channels
 __global__ __launch_bounds__(EW_THREADS) void dequant_kernel(const int32_t *__restrict__ acc, float *__restrict__ y,
                                                              size_t n, size_t channels, size_t inner, float scale,

@@ -63,6 +63,7 @@ struct LinesParams {
     // (the operations of dequant_kernel and relu_kernel, each rounded separately) instead of the int32 sums.
     int deq, act;
     float scale;
+    const float *scales;    // one scale per output channel (then `scale` is unused), or nullptr
     const float *bias;
     int xt_off[4];          // bytes into xt
     int out_off[4];         // elements into an output plane
@@ -82,7 +83,7 @@ struct LinesParams {
 // what is stored for the finished sum v of output channel n (see LinesParams::deq)
 __device__ __forceinline__ uint32_t finish_sum(const LinesParams &p, uint32_t v, int n) {
     if (!p.deq) return v;
-    float y = (float)(int32_t)v * p.scale;
+    float y = (float)(int32_t)v * (p.scales ? p.scales[n] : p.scale);
     if (p.bias) y = y + p.bias[n];
     if (p.act == 1) y = y > 0.0f ? y : 0.0f;
     return __float_as_uint(y);
@@ -338,11 +339,13 @@ __global__ void convt_border_fix_kernel(int32_t *__restrict__ out, const int32_t
 // (two-pass tables, transposed convolutions whose border terms are taken off afterwards, tanh outputs):
 // y = float(acc) * scale, + bias[c], then act (0 none, 1 max(y, 0), 2 tanh as in unary_kernel).
 __global__ __launch_bounds__(EW_THREADS) void finish_inplace_kernel(int32_t *__restrict__ buf, size_t n, size_t channels, size_t inner,
-                                                                    float scale, const float *__restrict__ bias, int act) {
+                                                                    float scale, const float *__restrict__ scales,
+                                                                    const float *__restrict__ bias, int act) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
     for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
-        float y = (float)buf[i] * scale;
-        if (bias) y = y + bias[(i / inner) % channels];
+        const size_t ch = (i / inner) % channels;
+        float y = (float)buf[i] * (scales ? scales[ch] : scale);
+        if (bias) y = y + bias[ch];
         if (act == 1) y = y > 0.0f ? y : 0.0f;
         else if (act == 2) y = tanh_spec(y);
         reinterpret_cast<float *>(buf)[i] = y;
@@ -354,6 +357,7 @@ __global__ __launch_bounds__(EW_THREADS) void finish_inplace_kernel(int32_t *__r
 __global__ __launch_bounds__(EW_THREADS) void reduce_partials_kernel(const int32_t *__restrict__ part, int ks, size_t stride_elems,
                                                                      int32_t *__restrict__ out, size_t n, int shift, int deq,
                                                                      size_t channels, size_t inner, float scale,
+                                                                     const float *__restrict__ scales,
                                                                      const float *__restrict__ bias, int act) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
     for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
@@ -362,8 +366,9 @@ __global__ __launch_bounds__(EW_THREADS) void reduce_partials_kernel(const int32
         if (shift >= 0) {
             out[i] = (int32_t)((uint32_t)out[i] + (v << shift));
         } else if (deq) {
-            float y = (float)(int32_t)v * scale;
-            if (bias) y = y + bias[(i / inner) % channels];
+            const size_t ch = (i / inner) % channels;
+            float y = (float)(int32_t)v * (scales ? scales[ch] : scale);
+            if (bias) y = y + bias[ch];
             if (act == 1) y = y > 0.0f ? y : 0.0f;
             else if (act == 2) y = tanh_spec(y);
             reinterpret_cast<float *>(out)[i] = y;

@@ -47,6 +47,7 @@ struct RowsParams {
     // max(y, 0) if act == 1, each operation rounded separately, instead of the int32 sum
     int deq, act;
     float scale;
+    const float *scales;    // one scale per output channel (then `scale` is unused), or nullptr
     const float *bias;
     // LSTM time step (lstm != 0; linear layer with N = 4 Hs whose offsets were packed in "cell order": packed column
     // 8 (u / 2) + 2 g + (u % 2) is gate g of hidden unit u, so the 8 columns of a workgroup are all four gates of two
@@ -61,7 +62,7 @@ struct RowsParams {
 
 __device__ __forceinline__ uint32_t finish_sum(const RowsParams &p, uint32_t v, int n) {
     if (!p.deq) return v;
-    float y = (float)(int32_t)v * p.scale;
+    float y = (float)(int32_t)v * (p.scales ? p.scales[n] : p.scale);
     if (p.bias) y = y + p.bias[n];
     if (p.act == 1) y = y > 0.0f ? y : 0.0f;
     return __float_as_uint(y);

@@ -751,3 +751,107 @@ def test_conv_transpose2d_layer_f32(B, kind, case):
         want = _oracle_layer(acc, s_out, Cout, acc.shape[2] * acc.shape[3], b, act)
         got = host(B.adapt_conv_transpose2d_layer_f32(pw, dev(x), s_x, s_out, pd, dev(b) if b is not None else None, act))
         assert bits_equal(got, want), (b is not None, act)
+
+
+# ------------------------------------------------------------------ per-channel ranges, percentile calibrator
+
+@pytest.mark.parametrize("shape", [(1, 1), (7, 45), (64, 576), (130, 1), (3, 5000)])
+def test_per_channel_quantiser_bit_exact(B, shape):
+    rows, cols = shape
+    rng = np.random.default_rng(rows * 31 + cols)
+    w = (rng.standard_normal((rows, cols)) * rng.uniform(0.01, 3.0, size=(rows, 1))).astype(np.float32)
+    if rows > 2:
+        w[1] = 0
+    amax = host(B.adapt_absmax_rows_f32(dev(w)))
+    assert bits_equal(amax, orc.absmax_rows(w))
+    for bits in (4, 8):
+        scales = np.array([orc.scale_from_amax(a, bits) for a in amax], dtype=np.float32)
+        q = host(B.adapt_quantize_rows_f32(dev(w), dev(scales), bits))
+        assert (q == orc.quantize_rows(w, scales, bits)).all()
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (5, 3, 7), (4, 16, 64), (64, 128, 1)])
+def test_per_channel_dequant_bit_exact(B, shape):
+    o, c, i = shape
+    rng = np.random.default_rng(sum(shape))
+    acc = rng.integers(-2**31, 2**31 - 1, size=shape, dtype=np.int64).astype(np.int32)
+    s = rng.uniform(1e-6, 1e-2, size=c).astype(np.float32)
+    b = rng.standard_normal(c).astype(np.float32)
+    for bias in (None, b):
+        got = host(B.adapt_dequant_i32_per_channel(dev(acc), dev(s), o, c, i, dev(bias) if bias is not None else None))
+        assert bits_equal(got, orc.dequant_per_channel(acc, s, o, c, i, bias))
+
+
+@pytest.mark.parametrize("n,bins", [(1, 1), (1000, 8), (100_003, 2048), (1 << 20, 4096), (5000, 100)])
+def test_histogram_and_percentile_bit_exact(B, n, bins):
+    rng = np.random.default_rng(n + bins)
+    x = (rng.standard_normal(n) ** 3).astype(np.float32)
+    if n > 10:
+        x[3] = np.nan
+    amax = orc.absmax(np.nan_to_num(x))
+    if not amax > 0:
+        amax = np.float32(1.0)
+    want = orc.histogram_abs(x, amax, bins)
+    counts = B.adapt_histogram_abs_f32(dev(x), amax, bins)
+    assert (host(counts).view(np.uint32) == want).all()
+    # a second batch accumulates into the same counters
+    y = (rng.standard_normal(n // 2 + 1) * np.float32(0.3) * amax).astype(np.float32)
+    want2 = orc.histogram_abs(y, amax, bins, want.copy())
+    B.adapt_histogram_abs_f32(dev(y), amax, bins, counts)
+    assert (host(counts).view(np.uint32) == want2).all()
+    for num, den in ((999, 1000), (1, 2), (1000, 1000), (0, 7)):
+        got = host(B.adapt_percentile_from_histogram(counts, amax, num, den))[0]
+        assert np.float32(got) == orc.percentile_from_histogram(want2, amax, num, den), (num, den)
+
+
+def test_conv_layer_with_per_channel_weights_and_percentile_activations(B):
+    """The paper's calibration recipe end to end on one layer: activation range from the 99.9 % histogram percentile,
+    weight ranges per output channel, 8-bit table; integers and rescaled outputs against the oracle."""
+    rng = np.random.default_rng(2024)
+    bits, bins = 8, 2048
+    x = (rng.standard_normal((4, 16, 12, 12)) ** 3).astype(np.float32)
+    w = (rng.standard_normal((24, 16, 3, 3)) * rng.uniform(0.05, 2.0, size=(24, 1, 1, 1))).astype(np.float32)
+    lut = wl.make_lut(bits)
+    # oracle side
+    amax = orc.absmax(x)
+    cmax = orc.percentile_from_histogram(orc.histogram_abs(x, amax, bins), amax)
+    s_x = orc.scale_from_amax(cmax, bits)
+    s_w = np.array([orc.scale_from_amax(a, bits) for a in orc.absmax_rows(w)], dtype=np.float32)
+    oqx, oqw = orc.quantize(x, s_x, bits), orc.quantize_rows(w, s_w, bits)
+    acc_w = orc.approx_conv2d(lut, bits, oqx, oqw, (1, 1), (1, 1), threads=4)
+    s_out = (np.float32(s_x) * s_w).astype(np.float32)
+    want = orc.dequant_per_channel(acc_w, s_out, 4, 24, 144)
+    # library side
+    xd, wd = dev(x), dev(w)
+    amax_g = np.float32(host(B.adapt_absmax_f32(xd))[0])
+    cmax_g = np.float32(host(B.adapt_percentile_from_histogram(B.adapt_histogram_abs_f32(xd, amax_g, bins), amax_g))[0])
+    assert amax_g == amax and cmax_g == cmax and cmax < amax
+    sw_g = np.array([orc.scale_from_amax(a, bits) for a in host(B.adapt_absmax_rows_f32(wd))], dtype=np.float32)
+    assert bits_equal(sw_g, s_w)
+    qx = B.adapt_quantize_f32(xd, s_x, bits)
+    qw = B.adapt_quantize_rows_f32(wd, dev(s_w), bits)
+    assert (host(qx) == oqx).all() and (host(qw) == oqw).all()
+    acc = B.adapt_approx_conv2d_packed(B.adapt_weights_pack_conv2d(B.Lut(lut, bits), qw), qx, (1, 1), (1, 1))
+    assert (host(acc) == acc_w).all()
+    y = B.adapt_dequant_i32_per_channel(acc, dev(s_out), 4, 24, 144)
+    assert bits_equal(host(y), want)
+    # and as one fused layer call with the vector of output scales (+ bias, ReLU)
+    bias = rng.standard_normal(24).astype(np.float32)
+    pw = B.adapt_weights_pack_conv2d(B.Lut(lut, bits), qw)
+    y2 = B.adapt_conv2d_layer_f32(pw, xd, s_x, dev(s_out), (1, 1), (1, 1), bias=dev(bias), act=B.ACT_RELU)
+    assert bits_equal(host(y2), orc.relu(orc.dequant_per_channel(acc_w, s_out, 4, 24, 144, bias)))
+    # a long linear layer and a transposed convolution take the same vector
+    Wl = (rng.standard_normal((24, 64)) * rng.uniform(0.05, 2.0, size=(24, 1))).astype(np.float32)
+    xl = rng.standard_normal((4200, 64)).astype(np.float32)
+    swl = np.array([orc.scale_from_amax(a, bits) for a in orc.absmax_rows(Wl)], dtype=np.float32)
+    sxl = orc.scale_from_amax(orc.absmax(xl), bits)
+    oql = orc.quantize_rows(Wl, swl, bits)
+    accl = orc.approx_linear(lut, bits, orc.quantize(xl, sxl, bits), oql, threads=4)
+    sol = (np.float32(sxl) * swl).astype(np.float32)
+    yl = B.adapt_linear_layer_f32(B.adapt_weights_pack_linear(B.Lut(lut, bits), dev(oql)), dev(xl), sxl, dev(sol))
+    assert bits_equal(host(yl), orc.dequant_per_channel(accl, sol, 4200, 24, 1))
+    wt = wl.random_i8(rng, (16, 24, 4, 4), bits, "gauss")
+    acct = orc.approx_conv_transpose2d(lut, bits, oqx, wt, 2, 1, threads=4)
+    yt = B.adapt_conv_transpose2d_layer_f32(B.adapt_weights_pack_conv_transpose2d(B.Lut(lut, bits), dev(wt), 2), xd, s_x, dev(s_out), 1,
+                                            bias=dev(bias), act=B.ACT_TANH)
+    assert bits_equal(host(yt), orc.tanh(orc.dequant_per_channel(acct, s_out, 4, 24, 24 * 24, bias)))
