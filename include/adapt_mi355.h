@@ -189,13 +189,16 @@ int adapt_approx_conv_transpose2d_packed(const adapt_weights *w, const int8_t *x
  * intermediates never reach memory.  y_dev has the shape of the int32 output of the corresponding *_packed call
  * and also serves as scratch for the sums where they cannot be rescaled in the product kernel.  s_out = s_x * s_w,
  * formed in fp32 by the caller; with per-channel weight ranges s_out_vec_dev [channels] holds s_x * s_w[c] instead
- * (then s_out is ignored; NULL otherwise); bias_dev [channels] or NULL.
+ * (then s_out is ignored; NULL otherwise); bias_dev [channels] or NULL.  The convolution also takes residual_dev,
+ * an fp32 tensor of the output's shape (not aliasing y_dev) or NULL: y = y + residual (adapt_add_f32) after the bias
+ * and before act -- the residual connection of a ResNet block without a pass of its own.
  * ---------------------------------------------------------------------------------------------- */
 int adapt_linear_layer_f32(const adapt_weights *w, const float *x_dev, float *y_dev, int M, float s_x, float s_out,
                            const float *s_out_vec_dev, const float *bias_dev, int act, void *stream);
 int adapt_conv2d_layer_f32(const adapt_weights *w, const float *x_dev, float *y_dev, int N, int H, int W, int stride_h,
                            int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, float s_x, float s_out,
-                           const float *s_out_vec_dev, const float *bias_dev, int act, void *stream);
+                           const float *s_out_vec_dev, const float *bias_dev, const float *residual_dev, int act,
+                           void *stream);
 int adapt_conv_transpose2d_layer_f32(const adapt_weights *w, const float *x_dev, float *y_dev, int N, int H, int W, int pad,
                                      float s_x, float s_out, const float *s_out_vec_dev, const float *bias_dev, int act,
                                      void *stream);

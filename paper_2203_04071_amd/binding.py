@@ -78,7 +78,7 @@ def load() -> ctypes.CDLL:
     L.adapt_approx_conv_transpose2d_packed.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
     L.adapt_weights_destroy.argtypes = [vp]
     L.adapt_linear_layer_f32.argtypes = [vp, vp, vp, i32, f32, f32, vp, vp, i32, vp]
-    L.adapt_conv2d_layer_f32.argtypes = [vp, vp, vp] + [i32] * 9 + [f32, f32, vp, vp, i32, vp]
+    L.adapt_conv2d_layer_f32.argtypes = [vp, vp, vp] + [i32] * 9 + [f32, f32, vp, vp, vp, i32, vp]
     L.adapt_conv_transpose2d_layer_f32.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, f32, vp, vp, i32, vp]
     L.adapt_approx_linear_packed.argtypes = [vp, vp, vp, i32, vp]
     L.adapt_approx_conv2d_packed.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
@@ -402,7 +402,7 @@ def adapt_linear_layer_f32(pw: PackedWeights, x, s_x, s_out, bias=None, act=ACT_
 
 
 def adapt_conv2d_layer_f32(pw: PackedWeights, x, s_x, s_out, stride=(1, 1), pad=(0, 0), dil=(1, 1), bias=None, act=ACT_NONE,
-                           out=None, stream=None):
+                           out=None, stream=None, residual=None):
     N, Cin, H, W = x.shape
     Cout, Cin2, kh, kw = pw.shape
     assert Cin == Cin2 and pw.kind == "conv2d"
@@ -411,8 +411,8 @@ def adapt_conv2d_layer_f32(pw: PackedWeights, x, s_x, s_out, stride=(1, 1), pad=
         out = torch.empty((N, Cout, Ho, Wo), dtype=torch.float32, device=x.device)
     sc, sv = _scales(s_out)
     _chk(load().adapt_conv2d_layer_f32(pw.handle, _ptr(x, torch.float32), _ptr(out, torch.float32), N, H, W, stride[0], stride[1],
-                                       pad[0], pad[1], dil[0], dil[1], float(s_x), sc, sv, _ptr(bias, torch.float32), act,
-                                       _stream(stream)))
+                                       pad[0], pad[1], dil[0], dil[1], float(s_x), sc, sv, _ptr(bias, torch.float32),
+                                       _ptr(residual, torch.float32), act, _stream(stream)))
     return out
 
 

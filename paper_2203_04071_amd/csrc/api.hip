@@ -83,12 +83,13 @@ struct LayerIO {
     float s_out = 1.0f;
     const float *s_out_vec = nullptr;   // one output scale per channel instead of s_out
     const float *bias = nullptr;
+    const float *resid = nullptr;       // fp32 tensor of the output's shape, added after the bias and before act
     // rescaling inside the product kernel needs a single table pass and an activation it knows
     bool fused(int storage) const { return deq && storage == 0 && act <= 1; }
 };
 
 int finish_inplace(int32_t *buf, size_t n, size_t channels, size_t inner, const LayerIO &io, hipStream_t s) {
-    adapt::finish_inplace_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, s>>>(buf, n, channels, inner, io.s_out, io.s_out_vec, io.bias, io.act);
+    adapt::finish_inplace_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, s>>>(buf, n, channels, inner, io.s_out, io.s_out_vec, io.bias, io.resid, io.act);
     HIP_TRY(hipGetLastError());
     return ADAPT_OK;
 }
@@ -567,6 +568,7 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     p.deq = fuse_in_kernel ? 1 : 0; p.act = fuse_in_kernel ? io->act : 0;
     p.scale = fuse_in_kernel ? io->s_out : 1.0f; p.bias = fuse_in_kernel ? io->bias : nullptr;
     p.scales = fuse_in_kernel ? io->s_out_vec : nullptr;
+    p.resid = fuse_in_kernel ? io->resid : nullptr;
     // one base offset per lane is enough when the R rows of a lane are equally spaced in xt
     const bool regular = (c.M % R == 0) && (c.HoWo == 1 || c.Wo % R == 0);
     const bool xmajor = c.xmajor && R == 8 && c.M % 8 == 0 && c.Wo % 4 == 0;
@@ -596,7 +598,8 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
         if (split && rc == ADAPT_OK) {
             adapt::reduce_partials_kernel<<<ew_grid(c.out_elems), adapt::EW_THREADS, 0, s>>>(
                 c.partial, pl.ksplit, c.out_elems, out, c.out_elems, half == 0 ? -1 : 16, (fuse && half == 0) ? 1 : 0, c.out_channels,
-                c.out_inner, fuse ? io->s_out : 1.0f, fuse ? io->s_out_vec : nullptr, fuse ? io->bias : nullptr, fuse ? io->act : 0);
+                c.out_inner, fuse ? io->s_out : 1.0f, fuse ? io->s_out_vec : nullptr, fuse ? io->bias : nullptr, fuse ? io->resid : nullptr,
+                fuse ? io->act : 0);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) rc = fail(ADAPT_ERR_HIP, "reduce_partials launch: %s", hipGetErrorString(e));
         }
@@ -796,8 +799,8 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io, !border);
     rc = ws_put(ws, xt, s, rc);
     if (rc != ADAPT_OK) return rc;
-    const int nrows = 2 * Ly < Ho ? 2 * Ly : Ho, ncols = 2 * Lx < Wo ? 2 * Lx : Wo;
     const size_t planes = (size_t)N * q.N;
+    const int nrows = 2 * Ly < Ho ? 2 * Ly : Ho, ncols = 2 * Lx < Wo ? 2 * Lx : Wo;
     const size_t work[2] = {planes * nrows * Wo, planes * (size_t)(Ho - nrows) * ncols};
     for (int region = 0; region < 2; ++region) {
         if (!work[region]) continue;
@@ -1327,7 +1330,7 @@ int adapt_linear_layer_f32(const adapt_weights *h, const float *x_dev, float *y_
 
 int adapt_conv2d_layer_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W, int stride_h, int stride_w,
                            int pad_h, int pad_w, int dil_h, int dil_w, float s_x, float s_out, const float *s_out_vec_dev,
-                           const float *bias_dev, int act, void *stream) {
+                           const float *bias_dev, const float *residual_dev, int act, void *stream) {
     const char *who = "adapt_conv2d_layer_f32";
     int rc = check_weights(h, 1, who);
     if (rc) return rc;
@@ -1340,6 +1343,8 @@ int adapt_conv2d_layer_f32(const adapt_weights *h, const float *x_dev, float *y_
     if (N == 0) return ADAPT_OK;
     LayerIO io;
     if ((rc = layer_io(&io, h, x_dev, y_dev, s_x, s_out, s_out_vec_dev, bias_dev, act, who))) return rc;
+    io.resid = residual_dev;
+    if (residual_dev == y_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: residual_dev must not alias y_dev", who);
     const long long xt_bytes = (long long)N * (H + 2LL * pad_h) * (W + 2LL * pad_w) * h->Cp;
     if (xt_bytes >= 0x7fffff00LL || (long long)N * h->N * Ho * Wo > 0x7fffffffLL || (long long)N * Ho * Wo > 0x7fffffffLL)
         return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);

@@ -65,6 +65,7 @@ struct LinesParams {
     float scale;
     const float *scales;    // one scale per output channel (then `scale` is unused), or nullptr
     const float *bias;
+    const float *resid;     // residual input: fp32 tensor of the output's shape added after the bias, before act; or nullptr
     int xt_off[4];          // bytes into xt
     int out_off[4];         // elements into an output plane
     long long dt_off[4];    // 16-byte units into dt
@@ -81,10 +82,12 @@ struct LinesParams {
 };
 
 // what is stored for the finished sum v of output channel n (see LinesParams::deq)
-__device__ __forceinline__ uint32_t finish_sum(const LinesParams &p, uint32_t v, int n) {
+// off: element offset of the output position (for the residual input)
+__device__ __forceinline__ uint32_t finish_sum(const LinesParams &p, uint32_t v, int n, size_t off) {
     if (!p.deq) return v;
     float y = (float)(int32_t)v * (p.scales ? p.scales[n] : p.scale);
     if (p.bias) y = y + p.bias[n];
+    if (p.resid) y = y + p.resid[off];
     if (p.act == 1) y = y > 0.0f ? y : 0.0f;
     return __float_as_uint(y);
 }
@@ -340,12 +343,14 @@ __global__ void convt_border_fix_kernel(int32_t *__restrict__ out, const int32_t
 // y = float(acc) * scale, + bias[c], then act (0 none, 1 max(y, 0), 2 tanh as in unary_kernel).
 __global__ __launch_bounds__(EW_THREADS) void finish_inplace_kernel(int32_t *__restrict__ buf, size_t n, size_t channels, size_t inner,
                                                                     float scale, const float *__restrict__ scales,
-                                                                    const float *__restrict__ bias, int act) {
+                                                                    const float *__restrict__ bias, const float *__restrict__ resid,
+                                                                    int act) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
     for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
         const size_t ch = (i / inner) % channels;
         float y = (float)buf[i] * (scales ? scales[ch] : scale);
         if (bias) y = y + bias[ch];
+        if (resid) y = y + resid[i];
         if (act == 1) y = y > 0.0f ? y : 0.0f;
         else if (act == 2) y = tanh_spec(y);
         reinterpret_cast<float *>(buf)[i] = y;
@@ -358,7 +363,8 @@ __global__ __launch_bounds__(EW_THREADS) void reduce_partials_kernel(const int32
                                                                      int32_t *__restrict__ out, size_t n, int shift, int deq,
                                                                      size_t channels, size_t inner, float scale,
                                                                      const float *__restrict__ scales,
-                                                                     const float *__restrict__ bias, int act) {
+                                                                     const float *__restrict__ bias, const float *__restrict__ resid,
+                                                                     int act) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
     for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
         uint32_t v = 0;
@@ -369,6 +375,7 @@ __global__ __launch_bounds__(EW_THREADS) void reduce_partials_kernel(const int32
             const size_t ch = (i / inner) % channels;
             float y = (float)(int32_t)v * (scales ? scales[ch] : scale);
             if (bias) y = y + bias[ch];
+            if (resid) y = y + resid[i];
             if (act == 1) y = y > 0.0f ? y : 0.0f;
             else if (act == 2) y = tanh_spec(y);
             reinterpret_cast<float *>(out)[i] = y;
@@ -620,7 +627,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_kernel(const LinesPar
                 const int img = r / p.HoWo, pix = r - img * p.HoWo;
                 const int a = pix / p.Wo, b = pix - a * p.Wo;
                 int32_t *q = p.out + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
-                if (p.shift < 0) *q = (int32_t)finish_sum(p, v, n);
+                if (p.shift < 0) *q = (int32_t)finish_sum(p, v, n, (size_t)(q - p.out));
                 else *q = (int32_t)((uint32_t)*q + (v << p.shift));
             }
         }
@@ -1000,7 +1007,6 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
                 v[i] = acc[i * 8];
 #pragma unroll
                 for (int c = 1; c < 8; ++c) v[i] = (j == c) ? acc[i * 8 + c] : v[i];
-                if (p.shift < 0) v[i] = finish_sum(p, v[i], n);
             }
             int img, a0, b0;
             row_pos(r0 < p.M ? r0 : 0, img, a0, b0);
@@ -1008,14 +1014,18 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
             for (int hq = 0; hq < 2; ++hq) {
                 if (r0 + 8 <= p.M) {        // M is a multiple of 8 here
                     int32_t *q0 = outp + ((size_t)img * p.N + n) * p.out_plane + out_off + a0 * p.out_sy + b0 * p.out_sx;
-                    if (p.shift < 0 && p.out_sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
-                        *reinterpret_cast<uint4 *>(q0) = make_uint4(v[4 * hq], v[4 * hq + 1], v[4 * hq + 2], v[4 * hq + 3]);
+                    const int sx = p.out_sx;
+                    uint32_t f[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        f[i] = p.shift < 0 ? finish_sum(p, v[4 * hq + i], n, (size_t)(q0 + i * sx - outp)) : v[4 * hq + i];
+                    if (p.shift < 0 && sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
+                        *reinterpret_cast<uint4 *>(q0) = make_uint4(f[0], f[1], f[2], f[3]);
                     } else {
-                        const int sx = p.out_sx;
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
-                            if (p.shift < 0) q0[i * sx] = (int32_t)v[4 * hq + i];
-                            else q0[i * sx] = (int32_t)((uint32_t)q0[i * sx] + (v[4 * hq + i] << p.shift));
+                            if (p.shift < 0) q0[i * sx] = (int32_t)f[i];
+                            else q0[i * sx] = (int32_t)((uint32_t)q0[i * sx] + (f[i] << p.shift));
                         }
                     }
                 }
@@ -1034,7 +1044,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
                     else { img = r / p.HoWo; pix = r - img * p.HoWo; }
                     const int a = pix / p.Wo, b = pix - a * p.Wo;
                     int32_t *q = outp + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
-                    if (p.shift < 0) *q = (int32_t)finish_sum(p, v, n);
+                    if (p.shift < 0) *q = (int32_t)finish_sum(p, v, n, (size_t)(q - outp));
                     else *q = (int32_t)((uint32_t)*q + (v << p.shift));
                 }
             }

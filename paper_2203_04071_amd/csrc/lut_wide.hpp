@@ -309,7 +309,6 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const Lin
             v[i] = acc[i * 8];
 #pragma unroll
             for (int c = 1; c < 8; ++c) v[i] = (j == c) ? acc[i * 8 + c] : v[i];
-            if (p.shift < 0) v[i] = finish_sum(p, v[i], n);
         }
         int img, a0, b0;
         row_pos(r0 < p.M ? r0 : 0, img, a0, b0);
@@ -317,14 +316,18 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const Lin
         for (int hq = 0; hq < 2; ++hq) {
             if (r0 + 8 <= p.M) {        // M is a multiple of 8 here
                 int32_t *q0 = outp + ((size_t)img * p.N + n) * p.out_plane + out_off + a0 * p.out_sy + b0 * p.out_sx;
-                if (p.shift < 0 && p.out_sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
-                    *reinterpret_cast<uint4 *>(q0) = make_uint4(v[4 * hq], v[4 * hq + 1], v[4 * hq + 2], v[4 * hq + 3]);
+                const int sx = p.out_sx;
+                uint32_t f[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    f[i] = p.shift < 0 ? finish_sum(p, v[4 * hq + i], n, (size_t)(q0 + i * sx - outp)) : v[4 * hq + i];
+                if (p.shift < 0 && sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
+                    *reinterpret_cast<uint4 *>(q0) = make_uint4(f[0], f[1], f[2], f[3]);
                 } else {
-                    const int sx = p.out_sx;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        if (p.shift < 0) q0[i * sx] = (int32_t)v[4 * hq + i];
-                        else q0[i * sx] = (int32_t)((uint32_t)q0[i * sx] + (v[4 * hq + i] << p.shift));
+                        if (p.shift < 0) q0[i * sx] = (int32_t)f[i];
+                        else q0[i * sx] = (int32_t)((uint32_t)q0[i * sx] + (f[i] << p.shift));
                     }
                 }
             }

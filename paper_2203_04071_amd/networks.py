@@ -78,7 +78,7 @@ class ResNet20:
         self.scales = None
         self.macs = None
 
-    def _conv(self, i, x, used, keep, relu=False):
+    def _conv(self, i, x, used, keep, relu=False, residual=None):
         """conv (+ ReLU).  Once the scales are frozen and nobody asks for the integer sums, the layer runs as one
         fused call (quantise while laying out the input, rescale + ReLU inside the product kernel)."""
         bits = self.bits
@@ -87,7 +87,7 @@ class ResNet20:
             s_x = self.scales[i]
             used.append(s_x)
             return B.adapt_conv2d_layer_f32(self.pws[i], x, s_x, _f(s_x) * _f(self.qws[i][1]), (st, st), (1, 1),
-                                            act=B.ACT_RELU if relu else B.ACT_NONE)
+                                            act=B.ACT_RELU if relu else B.ACT_NONE, residual=residual)
         s_x = calibrated_scale(x, bits) if self.scales is None else self.scales[i]
         used.append(s_x)
         qx = B.adapt_quantize_f32(x, s_x, bits)
@@ -96,6 +96,8 @@ class ResNet20:
             keep.append(acc)
         n, c, h, w = acc.shape
         y = B.adapt_dequant_i32(acc, _f(s_x) * _f(self.qws[i][1]), n, c, h * w)
+        if residual is not None:
+            return B.adapt_add_f32(y, residual, relu=relu)
         return B.adapt_relu_f32(y, out=y) if relu else y
 
     def forward(self, x, keep=None):
@@ -105,9 +107,8 @@ class ResNet20:
         while i < len(self.plan):
             cin, cout, stride = self.plan[i]
             y = self._conv(i, x, used, keep, relu=True)
-            z = self._conv(i + 1, y, used, keep)
             sc = x if (stride == 1 and cin == cout) else B.adapt_shortcut_a_f32(x, cout)
-            x = B.adapt_add_f32(z, sc, relu=True)
+            x = self._conv(i + 1, y, used, keep, relu=True, residual=sc)      # residual add + ReLU in the layer's epilogue
             i += 2
         pooled = B.adapt_avgpool_hw_f32(x)
         s_p = calibrated_scale(pooled, self.bits) if self.scales is None else self.scales[len(self.plan)]

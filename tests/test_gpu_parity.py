@@ -721,6 +721,14 @@ def test_conv2d_layer_f32(B, kind, case):
         want = _oracle_layer(acc, s_out, Cout, acc.shape[2] * acc.shape[3], b, act)
         got = host(B.adapt_conv2d_layer_f32(pw, dev(x), s_x, s_out, (st, st), (pd, pd), (1, 1), dev(b) if b is not None else None, act))
         assert bits_equal(got, want), (b is not None, act)
+    # residual input: y = act((float(acc) * s + bias) + residual)
+    res = rng.standard_normal(acc.shape).astype(np.float32)
+    for b, act in ((None, 0), (bias, 1)):
+        y = orc.add(orc.dequant(acc, s_out, N, Cout, acc.shape[2] * acc.shape[3], b), res)
+        want = (orc.relu(y) if act == 1 else y).reshape(acc.shape)
+        got = host(B.adapt_conv2d_layer_f32(pw, dev(x), s_x, s_out, (st, st), (pd, pd), (1, 1), dev(b) if b is not None else None, act,
+                                            residual=dev(res)))
+        assert bits_equal(got, want), ("residual", b is not None, act)
 
 
 LAYER_CONVT = [
