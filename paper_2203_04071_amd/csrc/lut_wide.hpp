@@ -291,40 +291,13 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const Lin
         advance_group();
     }
 
-    // Sum over the 8 k-sub lanes (j = 0..7) of a row slot as a reduce-scatter in three exchanges: in each, a lane keeps
-    // the half of its values that it will store, hands the other half to its partner and adds what the partner hands
-    // over.  Partners: 7 - j (splits on channel bit 1), j ^ 1 (splits on the run of 4 pixels), j ^ 2 (channel bit 0).
     // Lane j ends with run (j & 1) of channels (j >> 1) and (j >> 1) + 4: the two lanes of a pair write 32 adjacent
     // bytes, and the 8 row slots of a wave a whole 256-byte stretch of one channel in one instruction.
     const int r0 = mt * 1024 + rs * 8;
     if (r0 + 8 > p.M) return;               // M is a multiple of 8 here; no barrier follows
-    const bool k0 = j & 1, k1 = j & 2, k2 = j & 4;
     const int hq = j & 1, cq = j >> 1;
-    uint32_t s1[8][4];                      // [pixel][channel bit 0 + 2 * channel bit 2], channel bit 1 == k2
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int cc = 0; cc < 4; ++cc) {
-            const uint32_t lo = acc[i * 8 + (cc & 1) + 4 * (cc >> 1)], hi = acc[i * 8 + (cc & 1) + 4 * (cc >> 1) + 2];
-            const uint32_t keep = k2 ? hi : lo, give = k2 ? lo : hi;
-            s1[i][cc] = keep + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)give, 0x141, 0xF, 0xF, true);   // row_half_mirror
-        }
-    uint32_t s2[4][4];                      // [pixel of run k0][as above]
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int cc = 0; cc < 4; ++cc) {
-            const uint32_t keep = k0 ? s1[i + 4][cc] : s1[i][cc], give = k0 ? s1[i][cc] : s1[i + 4][cc];
-            s2[i][cc] = keep + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)give, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
-        }
-    uint32_t w[4][2];                       // [pixel][channel bit 2], channel bit 0 == k1
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const uint32_t keep = k1 ? s2[i][2 * t + 1] : s2[i][2 * t], give = k1 ? s2[i][2 * t] : s2[i][2 * t + 1];
-            w[i][t] = keep + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)give, 0x4E, 0xF, 0xF, true);      // quad_perm [2,3,0,1]
-        }
+    uint32_t w[4][2];
+    reduce_scatter_8x8(acc, j, w);
     int img, a0, b0;
     row_pos(r0 + 4 * hq, img, a0, b0);
 #pragma unroll
