@@ -459,33 +459,35 @@ __device__ __forceinline__ void accum8(uint32_t *acc, const u32x4_t v) {
     accum8<SIGNED>(acc, make_uint4(v.x, v.y, v.z, v.w));
 }
 
-// Sum of an 8 x 8 block of partial sums (acc[row * 8 + channel]) over the 8 k-sub lanes (j = 0..7) of a row slot,
+// Sum of an R x 8 block of partial sums (acc[row * 8 + channel]) over the 8 k-sub lanes (j = 0..7) of a row slot,
 // as a reduce-scatter in three exchanges: in each, a lane keeps the half of its values that it will store, hands
 // the other half to its partner and adds what the partner hands over.  Partners: 7 - j (splits on channel bit 1),
 // j ^ 1 (splits on the half of the rows), j ^ 2 (channel bit 0).  Lane j ends with w[i][t] = the complete sum of row
-// 4 * (j & 1) + i, channel (j >> 1) + 4 * t.  (Two thirds of the operations of summing everything everywhere and
-// then selecting, and few enough live registers that nothing spills.)
-__device__ __forceinline__ void reduce_scatter_8x8(const uint32_t *acc, int j, uint32_t (&w)[4][2]) {
+// (R / 2) * (j & 1) + i, channel (j >> 1) + 4 * t.  (Two thirds of the operations of summing everything everywhere
+// and then selecting, and few enough live registers that nothing spills.)
+template <int R>
+__device__ __forceinline__ void reduce_scatter(const uint32_t *acc, int j, uint32_t (&w)[R / 2][2]) {
+    static_assert(R % 2 == 0, "rows are split in two halves");
     const bool k0 = j & 1, k1 = j & 2, k2 = j & 4;
-    uint32_t s1[8][4];                      // [row][channel bit 0 + 2 * channel bit 2], channel bit 1 == k2
+    uint32_t s1[R][4];                      // [row][channel bit 0 + 2 * channel bit 2], channel bit 1 == k2
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < R; ++i)
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc) {
             const uint32_t lo = acc[i * 8 + (cc & 1) + 4 * (cc >> 1)], hi = acc[i * 8 + (cc & 1) + 4 * (cc >> 1) + 2];
             const uint32_t keep = k2 ? hi : lo, give = k2 ? lo : hi;
             s1[i][cc] = keep + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)give, 0x141, 0xF, 0xF, true);   // row_half_mirror
         }
-    uint32_t s2[4][4];                      // [row of half k0][as above]
+    uint32_t s2[R / 2][4];                  // [row of half k0][as above]
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < R / 2; ++i)
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc) {
-            const uint32_t keep = k0 ? s1[i + 4][cc] : s1[i][cc], give = k0 ? s1[i][cc] : s1[i + 4][cc];
+            const uint32_t keep = k0 ? s1[i + R / 2][cc] : s1[i][cc], give = k0 ? s1[i][cc] : s1[i + R / 2][cc];
             s2[i][cc] = keep + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)give, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
         }
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < R / 2; ++i)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const uint32_t keep = k1 ? s2[i][2 * t + 1] : s2[i][2 * t], give = k1 ? s2[i][2 * t] : s2[i][2 * t + 1];
@@ -640,51 +642,22 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_kernel(const LinesPar
         for (int i = 0; i < R; ++i) accum8<SIGNED>(acc + i * 8, rv[i]);
     }
 
-    if constexpr (R == 8) {
-        // lane j stores rows 4 * (j & 1) .. + 3 of channels (j >> 1) and (j >> 1) + 4
-        uint32_t w[4][2];
-        reduce_scatter_8x8(acc, j, w);
+    // lane j stores rows (R / 2) * (j & 1) .. + R / 2 - 1 of channels (j >> 1) and (j >> 1) + 4
+    uint32_t w[R / 2][2];
+    reduce_scatter<R>(acc, j, w);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = mt * (128 * R) + rs * R + 4 * (j & 1) + i;
-            if (r >= p.M) continue;
-            const int img = r / p.HoWo, pix = r - img * p.HoWo;
-            const int a = pix / p.Wo, b = pix - a * p.Wo;
+    for (int i = 0; i < R / 2; ++i) {
+        const int r = mt * (128 * R) + rs * R + (R / 2) * (j & 1) + i;
+        if (r >= p.M) continue;
+        const int img = r / p.HoWo, pix = r - img * p.HoWo;
+        const int a = pix / p.Wo, b = pix - a * p.Wo;
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const int n = nt * 8 + (j >> 1) + 4 * t;
-                if (n >= p.N) continue;
-                int32_t *q = p.out + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
-                if (p.shift < 0) *q = (int32_t)finish_sum(p, w[i][t], n, (size_t)(q - p.out));
-                else *q = (int32_t)((uint32_t)*q + (w[i][t] << p.shift));
-            }
-        }
-        return;
-    }
-    // reduce the partial sums of the 8 k-subs (lanes j = 0..7 of a row slot)
-#pragma unroll
-    for (int q = 0; q < R * 8; ++q) {
-        uint32_t v = acc[q];
-        v += __shfl_xor(v, 1, 64);
-        v += __shfl_xor(v, 2, 64);
-        v += __shfl_xor(v, 4, 64);
-        acc[q] = v;
-    }
-    const int n = nt * 8 + j;               // lane j stores channel j of its rows
-    if (n < p.N) {
-#pragma unroll
-        for (int i = 0; i < R; ++i) {
-            const int r = mt * (128 * R) + rs * R + i;
-            if (r < p.M) {
-                uint32_t v = acc[i * 8];
-#pragma unroll
-                for (int c = 1; c < 8; ++c) v = (j == c) ? acc[i * 8 + c] : v;
-                const int img = r / p.HoWo, pix = r - img * p.HoWo;
-                const int a = pix / p.Wo, b = pix - a * p.Wo;
-                int32_t *q = p.out + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
-                if (p.shift < 0) *q = (int32_t)finish_sum(p, v, n, (size_t)(q - p.out));
-                else *q = (int32_t)((uint32_t)*q + (v << p.shift));
-            }
+        for (int t = 0; t < 2; ++t) {
+            const int n = nt * 8 + (j >> 1) + 4 * t;
+            if (n >= p.N) continue;
+            int32_t *q = p.out + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
+            if (p.shift < 0) *q = (int32_t)finish_sum(p, w[i][t], n, (size_t)(q - p.out));
+            else *q = (int32_t)((uint32_t)*q + (w[i][t] << p.shift));
         }
     }
 }
@@ -1039,88 +1012,54 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     else
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" : "+v"(rv[0]) : : "memory");
 
-    if constexpr (R == 8) {
-        // lane j stores rows 4 * (j & 1) .. + 3 of channels (j >> 1) and (j >> 1) + 4; in the x-major form the rows are
-        // 4 consecutive pixels, so the two lanes of a pair write 32 adjacent bytes and the 8 row slots of a wave a
-        // whole 256-byte stretch of one channel in one instruction
-        uint32_t w[4][2];
-        reduce_scatter_8x8(acc, j, w);
-        const int r0 = mt * (128 * R) + rs * R + 4 * (j & 1);
-        if constexpr (XMAJOR) {
-            if (r0 + 4 > p.M) return;           // M is a multiple of 8 here
-            int img, a0, b0;
-            row_pos(r0, img, a0, b0);
+    // lane j stores rows (R / 2) * (j & 1) .. + R / 2 - 1 of channels (j >> 1) and (j >> 1) + 4; in the x-major form (R = 8)
+    // the rows are 4 consecutive pixels, so the two lanes of a pair write 32 adjacent bytes and the 8 row slots of
+    // a wave a whole 256-byte stretch of one channel in one instruction
+    uint32_t w[R / 2][2];
+    reduce_scatter<R>(acc, j, w);
+    const int r0 = mt * (128 * R) + rs * R + (R / 2) * (j & 1);
+    if constexpr (XMAJOR) {
+        static_assert(!XMAJOR || R == 8, "runs of 4 pixels");
+        if (r0 + 4 > p.M) return;           // M is a multiple of 8 here
+        int img, a0, b0;
+        row_pos(r0, img, a0, b0);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int n = nt * 8 + (j >> 1) + 4 * t;
+            if (n >= p.N) continue;
+            int32_t *q0 = outp + ((size_t)img * p.N + n) * p.out_plane + out_off + a0 * p.out_sy + b0 * p.out_sx;
+            const int sx = p.out_sx;
+            uint32_t f[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) f[i] = p.shift < 0 ? finish_sum(p, w[i][t], n, (size_t)(q0 + i * sx - outp)) : w[i][t];
+            if (p.shift < 0 && sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
+                *reinterpret_cast<uint4 *>(q0) = make_uint4(f[0], f[1], f[2], f[3]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (p.shift < 0) q0[i * sx] = (int32_t)f[i];
+                    else q0[i * sx] = (int32_t)((uint32_t)q0[i * sx] + (f[i] << p.shift));
+                }
+            }
+        }
+    } else {
+        int img0 = 0, pix0 = 0;
+        if (REGULAR) { img0 = r0 / p.HoWo; pix0 = r0 - img0 * p.HoWo; }
+#pragma unroll
+        for (int i = 0; i < R / 2; ++i) {
+            const int r = r0 + i;
+            if (r >= p.M) continue;
+            int img, pix;
+            if (REGULAR && p.HoWo > 1) { img = img0; pix = pix0 + i; }      // consecutive pixels of one output row
+            else { img = r / p.HoWo; pix = r - img * p.HoWo; }
+            const int a = pix / p.Wo, b = pix - a * p.Wo;
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 const int n = nt * 8 + (j >> 1) + 4 * t;
                 if (n >= p.N) continue;
-                int32_t *q0 = outp + ((size_t)img * p.N + n) * p.out_plane + out_off + a0 * p.out_sy + b0 * p.out_sx;
-                const int sx = p.out_sx;
-                uint32_t f[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) f[i] = p.shift < 0 ? finish_sum(p, w[i][t], n, (size_t)(q0 + i * sx - outp)) : w[i][t];
-                if (p.shift < 0 && sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
-                    *reinterpret_cast<uint4 *>(q0) = make_uint4(f[0], f[1], f[2], f[3]);
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        if (p.shift < 0) q0[i * sx] = (int32_t)f[i];
-                        else q0[i * sx] = (int32_t)((uint32_t)q0[i * sx] + (f[i] << p.shift));
-                    }
-                }
-            }
-        } else {
-            int img0 = 0, pix0 = 0;
-            if (REGULAR) { img0 = r0 / p.HoWo; pix0 = r0 - img0 * p.HoWo; }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = r0 + i;
-                if (r >= p.M) continue;
-                int img, pix;
-                if (REGULAR && p.HoWo > 1) { img = img0; pix = pix0 + i; }      // consecutive pixels of one output row
-                else { img = r / p.HoWo; pix = r - img * p.HoWo; }
-                const int a = pix / p.Wo, b = pix - a * p.Wo;
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const int n = nt * 8 + (j >> 1) + 4 * t;
-                    if (n >= p.N) continue;
-                    int32_t *q = outp + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
-                    if (p.shift < 0) *q = (int32_t)finish_sum(p, w[i][t], n, (size_t)(q - outp));
-                    else *q = (int32_t)((uint32_t)*q + (w[i][t] << p.shift));
-                }
-            }
-        }
-        return;
-    }
-    // reduce the partial sums of the 8 k-subs (lanes j = 0..7 of a row slot) with lane permutes inside
-    // the vector ALU: swap within pairs, within quads, then mirror the 8-lane half row
-#pragma unroll
-    for (int q = 0; q < R * 8; ++q) {
-        int v = (int)acc[q];
-        v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);      // quad_perm [1,0,3,2]
-        v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);      // quad_perm [2,3,0,1]
-        v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);     // row_half_mirror
-        acc[q] = (uint32_t)v;
-    }
-    const int n = nt * 8 + j;               // lane j stores channel j of its rows
-    if (n < p.N) {
-        const int r0 = mt * (128 * R) + rs * R;
-        int img0 = 0, pix0 = 0;
-        if (REGULAR) { img0 = r0 / p.HoWo; pix0 = r0 - img0 * p.HoWo; }
-#pragma unroll
-        for (int i = 0; i < R; ++i) {
-            const int r = r0 + i;
-            if (r < p.M) {
-                uint32_t v = acc[i * 8];
-#pragma unroll
-                for (int c = 1; c < 8; ++c) v = (j == c) ? acc[i * 8 + c] : v;
-                int img, pix;
-                if (REGULAR && p.HoWo > 1) { img = img0; pix = pix0 + i; }      // R consecutive pixels of one output row
-                else { img = r / p.HoWo; pix = r - img * p.HoWo; }
-                const int a = pix / p.Wo, b = pix - a * p.Wo;
                 int32_t *q = outp + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
-                if (p.shift < 0) *q = (int32_t)finish_sum(p, v, n, (size_t)(q - outp));
-                else *q = (int32_t)((uint32_t)*q + (v << p.shift));
+                if (p.shift < 0) *q = (int32_t)finish_sum(p, w[i][t], n, (size_t)(q - outp));
+                else *q = (int32_t)((uint32_t)*q + (w[i][t] << p.shift));
             }
         }
     }

@@ -297,7 +297,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const Lin
     if (r0 + 8 > p.M) return;               // M is a multiple of 8 here; no barrier follows
     const int hq = j & 1, cq = j >> 1;
     uint32_t w[4][2];
-    reduce_scatter_8x8(acc, j, w);
+    reduce_scatter<8>(acc, j, w);
     int img, a0, b0;
     row_pos(r0 + 4 * hq, img, a0, b0);
 #pragma unroll
