@@ -28,8 +28,8 @@ MODEL_CUS = 256
 
 # HBM bytes per launch of the dominant call, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, each
 # scaled by what the same counter reads for a plain 64 MiB copy (--copy-calibration); figures and commands are in
-# profiles/lut_lines_fast_config2.md.  Keyed by config number; None = not measured.
-MEASURED_TRAFFIC_BYTES = {2: (20759 * 2.0 + 14336 * 1.0 + 4646 * 2.0 + 2312 * 1.0) * 1024}
+# profiles/lut_lines_wide_config2.md.  Keyed by config number; None = not measured.
+MEASURED_TRAFFIC_BYTES = {2: (18576 * 2.0 + 8192 * 1.0 + 4646 * 2.0 + 2312 * 1.0) * 1024}
 
 
 def _f(x):
