@@ -280,3 +280,34 @@ def lstm_cell(acc_ih, acc_hh, s_ih, s_hh, bias, c):
     lib().orc_lstm_cell_f32(_p(acc_ih), _p(acc_hh), ctypes.c_float(float(s_ih)), ctypes.c_float(float(s_hh)),
                             _p(b) if b is not None else None, _p(c2), _p(h), L(B), L(Hs))
     return h, c2
+
+
+def gru_cell(acc_ih, acc_hh, s_ih, s_hh, b_ih, b_hh, h):
+    """Returns h_new [B][Hs]; gate order r, z, n along the 3*Hs axis."""
+    acc_ih = np.ascontiguousarray(acc_ih)
+    acc_hh = np.ascontiguousarray(acc_hh)
+    assert acc_ih.dtype == np.int32 and acc_hh.dtype == np.int32 and acc_ih.shape == acc_hh.shape
+    B, H3 = acc_ih.shape
+    Hs = H3 // 3
+    hp = _f32(h)
+    assert hp.shape == (B, Hs)
+    out = np.empty((B, Hs), dtype=np.float32)
+    bi = _f32(b_ih) if b_ih is not None else None
+    bh = _f32(b_hh) if b_hh is not None else None
+    lib().orc_gru_cell_f32(_p(acc_ih), _p(acc_hh), ctypes.c_float(float(s_ih)), ctypes.c_float(float(s_hh)),
+                           _p(bi) if bi is not None else None, _p(bh) if bh is not None else None, _p(hp), _p(out),
+                           L(B), L(Hs))
+    return out
+
+
+def rnn_cell(acc_ih, acc_hh, s_ih, s_hh, bias, relu=False):
+    """Returns h_new [B][Hs] = tanh (or ReLU) of the rescaled sums + bias."""
+    acc_ih = np.ascontiguousarray(acc_ih)
+    acc_hh = np.ascontiguousarray(acc_hh)
+    assert acc_ih.dtype == np.int32 and acc_hh.dtype == np.int32 and acc_ih.shape == acc_hh.shape
+    B, Hs = acc_ih.shape
+    out = np.empty((B, Hs), dtype=np.float32)
+    b = _f32(bias) if bias is not None else None
+    lib().orc_rnn_cell_f32(_p(acc_ih), _p(acc_hh), ctypes.c_float(float(s_ih)), ctypes.c_float(float(s_hh)),
+                           _p(b) if b is not None else None, ctypes.c_int(1 if relu else 0), _p(out), L(B), L(Hs))
+    return out

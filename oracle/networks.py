@@ -122,3 +122,77 @@ def dcgan(cfg, scales=None, threads=1, keep=False):
         y = orc.dequant(acc, _f(s_x) * _f(s_w), n, c, h * wd)
         x = orc.tanh(y) if i == nl - 1 else orc.relu(y)
     return dict(out=x, scales=used, accs=accs, last_acc=acc)
+
+
+def _recurrent_inputs(cfg, gates, threads, steps):
+    """Shared front part of the recurrent runners: quantised weights, scales, and the input sums of all steps."""
+    bits, lut = cfg["bits"], cfg["lut"]
+    x = cfg["x"]
+    T, B, I = x.shape
+    if steps is not None:
+        T = min(T, steps)
+    Hs = cfg["w_hh"].shape[1]
+    assert cfg["w_ih"].shape == (gates * Hs, I) and cfg["w_hh"].shape == (gates * Hs, Hs)
+    Q = (1 << (bits - 1)) - 1
+    q_wih, s_wih = quantize_weights(cfg["w_ih"], bits)
+    q_whh, s_whh = quantize_weights(cfg["w_hh"], bits)
+    s_x = orc.scale_from_amax(orc.absmax(x), bits)       # over the whole [T, B, I] input
+    s_h = _f(1.0) / _f(Q)                                # |h| < 1
+    qx = orc.quantize(x[:T], s_x, bits).reshape(T * B, I)
+    acc_ih = orc.approx_linear(lut, bits, qx, q_wih, threads).reshape(T, B, gates * Hs)
+    return T, B, Hs, q_whh, s_wih, s_whh, s_x, s_h, acc_ih
+
+
+def gru(cfg, threads=1, steps=None):
+    """Single-layer GRU whose gate pre-activations are approximate linear layers (Sec. III-B "RNN Layer");
+    gates and the state update in fp32.  cfg: x [T][B][I], w_ih [3 Hs][I], w_hh [3 Hs][Hs], b_ih, b_hh [3 Hs]."""
+    bits, lut = cfg["bits"], cfg["lut"]
+    T, B, Hs, q_whh, s_wih, s_whh, s_x, s_h, acc_ih = _recurrent_inputs(cfg, 3, threads, steps)
+    h = np.zeros((B, Hs), dtype=np.float32)
+    hs = np.empty((T, B, Hs), dtype=np.float32)
+    acc_hh = None
+    for t in range(T):
+        qh = orc.quantize(h, s_h, bits)
+        acc_hh = orc.approx_linear(lut, bits, qh, q_whh, threads)
+        h = orc.gru_cell(acc_ih[t], acc_hh, _f(s_x) * _f(s_wih), _f(s_h) * _f(s_whh), cfg["b_ih"], cfg["b_hh"], h)
+        hs[t] = h
+    return dict(hs=hs, acc_ih=acc_ih, acc_hh_last=acc_hh, s_x=s_x, s_h=s_h, s_wih=s_wih, s_whh=s_whh)
+
+
+def rnn(cfg, threads=1, steps=None):
+    """Single-layer tanh recurrent layer, h_t = tanh(W_ih x_t + W_hh h_(t-1) + b) with approximate linear layers
+    (Sec. III-B "RNN Layer").  cfg: x [T][B][I], w_ih [Hs][I], w_hh [Hs][Hs], bias [Hs]."""
+    bits, lut = cfg["bits"], cfg["lut"]
+    T, B, Hs, q_whh, s_wih, s_whh, s_x, s_h, acc_ih = _recurrent_inputs(cfg, 1, threads, steps)
+    h = np.zeros((B, Hs), dtype=np.float32)
+    hs = np.empty((T, B, Hs), dtype=np.float32)
+    acc_hh = None
+    for t in range(T):
+        qh = orc.quantize(h, s_h, bits)
+        acc_hh = orc.approx_linear(lut, bits, qh, q_whh, threads)
+        h = orc.rnn_cell(acc_ih[t], acc_hh, _f(s_x) * _f(s_wih), _f(s_h) * _f(s_whh), cfg["bias"], relu=False)
+        hs[t] = h
+    return dict(hs=hs, acc_ih=acc_ih, acc_hh_last=acc_hh, s_x=s_x, s_h=s_h, s_wih=s_wih, s_whh=s_whh)
+
+
+def separable_conv(cfg, scales=None, threads=1):
+    """Separable convolution (Sec. III-B "Separable convolution", eq. (1)): a depthwise convolution (groups = Cin)
+    followed by a pointwise 1x1 convolution, each an approximate layer of its own (quantise -> table-lookup
+    convolution -> dequantise).  cfg: x [N][Cin][H][W], w_dw [Cin][1][kh][kw], w_pw [Cout][Cin][1][1], stride, pad."""
+    bits, lut = cfg["bits"], cfg["lut"]
+    x = cfg["x"]
+    Cin = x.shape[1]
+    q_dw, s_dw = quantize_weights(cfg["w_dw"], bits)
+    q_pw, s_pw = quantize_weights(cfg["w_pw"], bits)
+    s_x = scales[0] if scales is not None else orc.scale_from_amax(orc.absmax(x), bits)
+    qx = orc.quantize(x, s_x, bits)
+    st, pd = cfg["stride"], cfg["pad"]
+    acc_dw = orc.approx_conv2d(lut, bits, qx, q_dw, (st, st), (pd, pd), groups=Cin, threads=threads)
+    n, c, h, w = acc_dw.shape
+    y = orc.dequant(acc_dw, _f(s_x) * _f(s_dw), n, c, h * w)
+    s_y = scales[1] if scales is not None else orc.scale_from_amax(orc.absmax(y), bits)
+    qy = orc.quantize(y, s_y, bits)
+    acc_pw = orc.approx_conv2d(lut, bits, qy, q_pw, threads=threads)
+    n, c, h, w = acc_pw.shape
+    out = orc.dequant(acc_pw, _f(s_y) * _f(s_pw), n, c, h * w)
+    return dict(out=out, y=y, acc_dw=acc_dw, acc_pw=acc_pw, scales=[s_x, s_y], s_dw=s_dw, s_pw=s_pw)

@@ -456,3 +456,48 @@ void orc_lstm_cell_f32(const int32_t *acc_ih, const int32_t *acc_hh, float s_ih,
             h[b * Hs + j] = og * orc_tanh_f32(cn);
         }
 }
+
+/* GRU memory cell (Sec. III-B "RNN Layer": equivalent to the library layer), gate order r, z, n:
+ *   gi = float(acc_ih)*s_ih + b_ih;   gh = float(acc_hh)*s_hh + b_hh        (per gate; a NULL bias adds nothing)
+ *   r = sigmoid(gi_r + gh_r);  z = sigmoid(gi_z + gh_z);  n = tanh(gi_n + r*gh_n)   (product, then sum)
+ *   h' = (1 - z)*n + z*h                                                    (two products, one sum)
+ * acc_ih, acc_hh: [B][3*Hs];  h_prev, h_out: [B][Hs] (may be the same array). */
+void orc_gru_cell_f32(const int32_t *acc_ih, const int32_t *acc_hh, float s_ih, float s_hh,
+                      const float *b_ih, const float *b_hh, const float *h_prev, float *h_out, long B, long Hs) {
+    for (long b = 0; b < B; ++b)
+        for (long j = 0; j < Hs; ++j) {
+            float gi[3], gh[3];
+            for (int g = 0; g < 3; ++g) {
+                const long idx = b * 3 * Hs + g * Hs + j;
+                float u = (float)acc_ih[idx] * s_ih;
+                if (b_ih) u = u + b_ih[g * Hs + j];
+                float v = (float)acc_hh[idx] * s_hh;
+                if (b_hh) v = v + b_hh[g * Hs + j];
+                gi[g] = u;
+                gh[g] = v;
+            }
+            const float r = orc_sigmoid_f32(gi[0] + gh[0]);
+            const float z = orc_sigmoid_f32(gi[1] + gh[1]);
+            const float rn = r * gh[2];
+            const float n = orc_tanh_f32(gi[2] + rn);
+            const float omz = 1.0f - z;
+            const float a = omz * n;
+            const float c = z * h_prev[b * Hs + j];
+            h_out[b * Hs + j] = a + c;
+        }
+}
+
+/* Plain recurrent cell (Sec. III-B "RNN Layer"): h' = act((float(acc_ih)*s_ih + float(acc_hh)*s_hh) + bias),
+ * act = tanh (relu == 0) or max(., 0) (relu != 0).  acc_ih, acc_hh, h_out: [B][Hs]; bias [Hs] or NULL. */
+void orc_rnn_cell_f32(const int32_t *acc_ih, const int32_t *acc_hh, float s_ih, float s_hh, const float *bias,
+                      int relu, float *h_out, long B, long Hs) {
+    for (long b = 0; b < B; ++b)
+        for (long j = 0; j < Hs; ++j) {
+            const long idx = b * Hs + j;
+            const float u = (float)acc_ih[idx] * s_ih;
+            const float v = (float)acc_hh[idx] * s_hh;
+            float s = u + v;
+            s = s + (bias ? bias[j] : 0.0f);
+            h_out[idx] = relu ? (s > 0.0f ? s : 0.0f) : orc_tanh_f32(s);
+        }
+}

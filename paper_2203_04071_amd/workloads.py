@@ -129,6 +129,35 @@ def config5(bits: int = 8, seed: int = DATA_SEED_BASE + 5, batch: int = 256) -> 
     return dict(bits=bits, z=z, ws=ws, lut=make_lut(bits), plan=list(DCGAN_PLAN))
 
 
+def recurrent_workload(kind: str = "gru", seed: int = DATA_SEED_BASE + 40, seq: int = 20, batch: int = 16, isz: int = 128,
+                       hsz: int = 128, bits: int = 8) -> dict:
+    """Single-layer GRU ("gru": 3 gates, two bias vectors) or plain tanh recurrent layer ("rnn": one gate, one bias);
+    weights N(0, std 0.1), biases N(0, std 0.05), inputs N(0, 1) — the recipe of the LSTM configuration."""
+    gates = {"gru": 3, "rnn": 1}[kind]
+    rng = np.random.default_rng(seed + (0 if kind == "gru" else 1))
+    x = rng.standard_normal((seq, batch, isz), dtype=np.float32)
+    w_ih = (rng.standard_normal((gates * hsz, isz), dtype=np.float32) * np.float32(0.1)).astype(np.float32)
+    w_hh = (rng.standard_normal((gates * hsz, hsz), dtype=np.float32) * np.float32(0.1)).astype(np.float32)
+    cfg = dict(bits=bits, x=x, w_ih=w_ih, w_hh=w_hh, lut=make_lut(bits))
+    if kind == "gru":
+        cfg["b_ih"] = (rng.standard_normal(3 * hsz, dtype=np.float32) * np.float32(0.05)).astype(np.float32)
+        cfg["b_hh"] = (rng.standard_normal(3 * hsz, dtype=np.float32) * np.float32(0.05)).astype(np.float32)
+    else:
+        cfg["bias"] = (rng.standard_normal(hsz, dtype=np.float32) * np.float32(0.05)).astype(np.float32)
+    return cfg
+
+
+def separable_workload(seed: int = DATA_SEED_BASE + 42, batch: int = 8, cin: int = 32, cout: int = 64, hw: int = 16,
+                       k: int = 3, stride: int = 1, bits: int = 8) -> dict:
+    """Separable convolution block: depthwise k x k (groups = cin, pad k // 2) then pointwise 1 x 1; He-normal weights,
+    inputs N(0, 1)."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((batch, cin, hw, hw), dtype=np.float32)
+    w_dw = (rng.standard_normal((cin, 1, k, k), dtype=np.float32) * np.float32(np.sqrt(2.0 / (k * k)))).astype(np.float32)
+    w_pw = (rng.standard_normal((cout, cin, 1, 1), dtype=np.float32) * np.float32(np.sqrt(2.0 / cin))).astype(np.float32)
+    return dict(bits=bits, x=x, w_dw=w_dw, w_pw=w_pw, stride=stride, pad=k // 2, lut=make_lut(bits))
+
+
 def lut_macs_conv2d(n, cin, h, w, cout, kh, kw, sh, sw, ph, pw, dh=1, dw=1, groups=1) -> int:
     """Number of table terms of a convolution, padded taps included."""
     ho = (h + 2 * ph - dh * (kh - 1) - 1) // sh + 1

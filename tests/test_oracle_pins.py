@@ -376,6 +376,103 @@ def test_lstm_cell_matches_library_lstm_with_exact_table():
     assert np.abs(out["c"] - cn[0].numpy()).max() < 0.05
 
 
+def test_gru_and_rnn_cells_match_library_layers_with_exact_table():
+    """Exact-product 8-bit GRU / tanh RNN track torch.nn.GRU (gate order r, z, n; b_hn inside the reset product) and
+    torch.nn.RNN to quantisation noise; a wrong gate order, a swapped bias or r applied to the input half fails."""
+    from oracle import networks
+    rng = np.random.default_rng(5)
+    T, B, I, Hs = 6, 3, 16, 8
+    cfg = dict(bits=8, lut=wl.exact_lut(8),
+               x=rng.standard_normal((T, B, I)).astype(np.float32),
+               w_ih=(rng.standard_normal((3 * Hs, I)) * 0.3).astype(np.float32),
+               w_hh=(rng.standard_normal((3 * Hs, Hs)) * 0.3).astype(np.float32),
+               b_ih=(rng.standard_normal(3 * Hs) * 0.5).astype(np.float32),
+               b_hh=(rng.standard_normal(3 * Hs) * 0.5).astype(np.float32))
+    out = networks.gru(cfg)
+    m = torch.nn.GRU(I, Hs)
+    with torch.no_grad():
+        m.weight_ih_l0.copy_(torch.from_numpy(cfg["w_ih"]))
+        m.weight_hh_l0.copy_(torch.from_numpy(cfg["w_hh"]))
+        m.bias_ih_l0.copy_(torch.from_numpy(cfg["b_ih"]))
+        m.bias_hh_l0.copy_(torch.from_numpy(cfg["b_hh"]))
+        ref, _ = m(torch.from_numpy(cfg["x"]))
+    assert np.abs(out["hs"] - ref.numpy()).max() < 0.03
+
+    cfg = dict(bits=8, lut=wl.exact_lut(8),
+               x=rng.standard_normal((T, B, I)).astype(np.float32),
+               w_ih=(rng.standard_normal((Hs, I)) * 0.3).astype(np.float32),
+               w_hh=(rng.standard_normal((Hs, Hs)) * 0.3).astype(np.float32),
+               bias=(rng.standard_normal(Hs) * 0.5).astype(np.float32))
+    out = networks.rnn(cfg)
+    m = torch.nn.RNN(I, Hs, nonlinearity="tanh")
+    with torch.no_grad():
+        m.weight_ih_l0.copy_(torch.from_numpy(cfg["w_ih"]))
+        m.weight_hh_l0.copy_(torch.from_numpy(cfg["w_hh"]))
+        m.bias_ih_l0.copy_(torch.from_numpy(cfg["bias"]))
+        m.bias_hh_l0.zero_()
+        ref, _ = m(torch.from_numpy(cfg["x"]))
+    assert np.abs(out["hs"] - ref.numpy()).max() < 0.06       # no gates: quantisation noise of h feeds straight back
+
+
+def test_gru_and_rnn_cells_closed_forms():
+    """Saturated gates give closed forms: z = 1 keeps h exactly; z = 0, r = 0 gives tanh of the input half alone;
+    the plain cell is tanh / ReLU of the rescaled sum, each operation rounded separately."""
+    rng = np.random.default_rng(6)
+    B, Hs = 4, 5
+    acc_ih = rng.integers(-2000, 2000, (B, 3 * Hs)).astype(np.int32)
+    acc_hh = rng.integers(-2000, 2000, (B, 3 * Hs)).astype(np.int32)
+    h = rng.uniform(-1, 1, (B, Hs)).astype(np.float32)
+    s_ih, s_hh = np.float32(1e-3), np.float32(2e-3)
+    big = np.float32(200.0)
+    b = np.zeros(3 * Hs, np.float32)
+    b[Hs:2 * Hs] = big                                   # z -> 1
+    assert (orc.gru_cell(acc_ih, acc_hh, s_ih, s_hh, b, None, h) == h).all()
+    b[:] = 0
+    b[:2 * Hs] = -big                                    # r -> 0 and z -> 0 (both exactly 0 after rounding 1 / (1 + e^88))
+    got = orc.gru_cell(acc_ih, acc_hh, s_ih, s_hh, b, None, h)
+    r = orc.sigmoid((acc_ih[:, :Hs].astype(np.float32) * s_ih - big) + acc_hh[:, :Hs].astype(np.float32) * s_hh)
+    z = orc.sigmoid((acc_ih[:, Hs:2 * Hs].astype(np.float32) * s_ih - big) + acc_hh[:, Hs:2 * Hs].astype(np.float32) * s_hh)
+    gi_n = acc_ih[:, 2 * Hs:].astype(np.float32) * s_ih
+    gh_n = acc_hh[:, 2 * Hs:].astype(np.float32) * s_hh
+    n = orc.tanh(gi_n + r * gh_n)
+    want = (np.float32(1) - z) * n + z * h
+    assert (got == want).all()
+    assert np.abs(got - np.tanh(gi_n.astype(np.float64))).max() < 1e-6        # r, z vanish: the input half alone
+    # b_hh of the candidate gate sits inside the reset product: with r -> 0 it must not matter
+    bh = np.zeros(3 * Hs, np.float32)
+    bh[2 * Hs:] = np.float32(0.7)
+    assert np.abs(orc.gru_cell(acc_ih, acc_hh, s_ih, s_hh, b, bh, h) - got).max() < 1e-6
+    # plain cell
+    a1 = acc_ih[:, :Hs].copy()
+    a2 = acc_hh[:, :Hs].copy()
+    bias = rng.standard_normal(Hs).astype(np.float32)
+    pre = (a1.astype(np.float32) * s_ih + a2.astype(np.float32) * s_hh) + bias
+    assert (orc.rnn_cell(a1, a2, s_ih, s_hh, bias, relu=False) == orc.tanh(pre)).all()
+    assert (orc.rnn_cell(a1, a2, s_ih, s_hh, bias, relu=True) == np.maximum(pre, np.float32(0))).all()
+    pre0 = a1.astype(np.float32) * s_ih + a2.astype(np.float32) * s_hh
+    assert (orc.rnn_cell(a1, a2, s_ih, s_hh, None, relu=True) == np.maximum(pre0, np.float32(0))).all()
+
+
+def test_separable_convolution_is_depthwise_then_pointwise():
+    """Eq. (1): with the exact table the separable block tracks conv2d(groups = Cin) followed by a 1x1 conv2d."""
+    from oracle import networks
+    F = torch.nn.functional
+    cfg = wl.separable_workload(batch=2, cin=6, cout=5, hw=7, stride=2)
+    cfg["lut"] = wl.exact_lut(8)
+    out = networks.separable_conv(cfg)
+    x = torch.from_numpy(cfg["x"])
+    y = F.conv2d(x, torch.from_numpy(cfg["w_dw"]), stride=2, padding=1, groups=6)
+    ref = F.conv2d(y, torch.from_numpy(cfg["w_pw"])).numpy()
+    assert out["out"].shape == ref.shape == (2, 5, 4, 4)
+    assert np.linalg.norm(out["out"] - ref) / np.linalg.norm(ref) < 0.03
+    # the depthwise sums are the integer depthwise convolution of the quantised operands
+    qx = orc.quantize(cfg["x"], out["scales"][0], 8)
+    qw, _ = networks.quantize_weights(cfg["w_dw"], 8)
+    want = F.conv2d(torch.from_numpy(qx.astype(np.float64)), torch.from_numpy(qw.astype(np.float64)), stride=2, padding=1,
+                    groups=6).numpy()
+    assert (out["acc_dw"].astype(np.float64) == want).all()
+
+
 def test_network_runners_track_fp32_networks_with_exact_table():
     """ResNet-style and generator-style runners with the exact 8-bit table stay close to the
     same networks evaluated in fp32 by library convolutions (loose: quantisation noise only)."""
