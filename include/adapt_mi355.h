@@ -45,7 +45,7 @@ extern "C" {
 
 #define ADAPT_OK 0
 #define ADAPT_ERR_INVALID_ARGUMENT (-1) /* null pointer, bits outside [2,8], non-positive dims, bad geometry */
-#define ADAPT_ERR_UNSUPPORTED (-2)      /* valid request this build does not implement (e.g. groups > 1) */
+#define ADAPT_ERR_UNSUPPORTED (-2)      /* valid request this build does not implement */
 #define ADAPT_ERR_LUT_RANGE (-3)        /* reserved: table entry not representable */
 #define ADAPT_ERR_HIP (-4)              /* a HIP runtime call or kernel launch failed */
 #define ADAPT_ERR_OUT_OF_MEMORY (-5)
@@ -127,7 +127,9 @@ int adapt_approx_linear(const adapt_lut *lut, const int8_t *a_dev, const int8_t 
  * Hout = (H + 2 pad_h - dil_h (kh-1) - 1) / stride_h + 1 (likewise Wout).  The layer is the product of
  * the expanded input matrix with the filter matrix (Sec. III-B); a tap that falls into the padding is
  * an entry of that matrix equal to quantised zero, so T[0][w] IS added for it.
- * groups must be 1 in this build (else ADAPT_ERR_UNSUPPORTED). */
+ * groups > 1 (Sec. III-B: "groups"; groups = Cin is the depthwise half of the separable convolution, eq. (1)):
+ * output channel co belongs to group co / (Cout / groups) and meets only the Cin / groups input channels of that
+ * group.  Cin and Cout must be multiples of groups (else ADAPT_ERR_INVALID_ARGUMENT). */
 int adapt_approx_conv2d(const adapt_lut *lut, const int8_t *x_dev, const int8_t *w_dev, int32_t *acc_dev,
                         int N, int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w,
                         int pad_h, int pad_w, int dil_h, int dil_w, int groups, void *stream);
@@ -235,6 +237,23 @@ int adapt_lstm_cell_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, fl
 int adapt_lstm_cell_q_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh,
                           const float *bias_dev, float *c_dev, float *h_dev, int8_t *qh_dev, float s_h, int bits, int B,
                           int Hs, void *stream);
+
+/* GRU memory cell (Sec. III-B "RNN Layer"), gate order r, z, n along the 3*Hs axis, every operation one rounded
+ * fp32 operation in this order:
+ *   gi = float(acc_ih) * s_ih + b_ih;  gh = float(acc_hh) * s_hh + b_hh      (a NULL bias adds nothing)
+ *   r = sigmoid(gi_r + gh_r);  z = sigmoid(gi_z + gh_z);  n = tanh(gi_n + r * gh_n);  h' = (1 - z) * n + z * h
+ * acc_ih_dev, acc_hh_dev [B][3 Hs] int32; b_ih_dev, b_hh_dev [3 Hs] or NULL; h_prev_dev, h_dev [B][Hs] (may be the
+ * same buffer).  qh_dev [B][Hs] int8 or NULL: when given, also qh = quantise(h', s_h, bits) as adapt_quantize_f32. */
+int adapt_gru_cell_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh,
+                       const float *b_ih_dev, const float *b_hh_dev, const float *h_prev_dev, float *h_dev,
+                       int8_t *qh_dev, float s_h, int bits, int B, int Hs, void *stream);
+
+/* Plain recurrent cell (Sec. III-B "RNN Layer"): h' = act((float(acc_ih) * s_ih + float(acc_hh) * s_hh) + bias),
+ * act = tanh (relu == 0) or max(., 0) (relu != 0).  acc_ih_dev, acc_hh_dev, h_dev [B][Hs]; bias_dev [Hs] or NULL;
+ * qh_dev as above. */
+int adapt_rnn_cell_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh,
+                       const float *bias_dev, int relu, float *h_dev, int8_t *qh_dev, float s_h, int bits, int B, int Hs,
+                       void *stream);
 
 /* One whole time step of the recurrent part of an LSTM layer in one kernel:
  *     acc_hh = table product of qh_dev [B][Hs] with the packed W_hh [4 Hs][Hs]   (adapt_approx_linear_packed)

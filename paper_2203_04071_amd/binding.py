@@ -31,7 +31,7 @@ EXPORTS = [
     "adapt_approx_linear_packed", "adapt_approx_conv2d_packed", "adapt_approx_conv_transpose2d_packed",
     "adapt_linear_layer_f32", "adapt_conv2d_layer_f32", "adapt_conv_transpose2d_layer_f32",
     "adapt_relu_f32", "adapt_add_f32", "adapt_avgpool_hw_f32", "adapt_shortcut_a_f32",
-    "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32", "adapt_lstm_cell_q_f32", "adapt_lstm_step_f32",
+    "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32", "adapt_lstm_cell_q_f32", "adapt_lstm_step_f32", "adapt_gru_cell_f32", "adapt_rnn_cell_f32",
 ]
 
 
@@ -91,6 +91,8 @@ def load() -> ctypes.CDLL:
     L.adapt_lstm_cell_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, i32, i32, vp]
     L.adapt_lstm_step_f32.argtypes = [vp, vp, vp, f32, f32, f32, vp, vp, vp, vp, i32, i32, vp]
     L.adapt_lstm_cell_q_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, vp, f32, i32, i32, i32, vp]
+    L.adapt_gru_cell_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, vp, vp, f32, i32, i32, i32, vp]
+    L.adapt_rnn_cell_f32.argtypes = [vp, vp, f32, f32, vp, i32, vp, vp, f32, i32, i32, i32, vp]
     for name in EXPORTS:
         if name != "adapt_last_error":
             getattr(L, name).restype = i32
@@ -377,6 +379,25 @@ def adapt_lstm_cell_q_f32(acc_ih, acc_hh, s_ih: float, s_hh: float, bias, c, h, 
                                       _ptr(bias, torch.float32), _ptr(c, torch.float32), _ptr(h, torch.float32),
                                       _ptr(qh, torch.int8), float(s_h), bits, B, Hs, _stream(stream)))
     return h, c, qh
+
+
+def adapt_gru_cell_f32(acc_ih, acc_hh, s_ih: float, s_hh: float, b_ih, b_hh, h_prev, h, qh=None, s_h: float = 1.0, bits: int = 8,
+                       stream=None):
+    B, H3 = acc_ih.shape
+    Hs = H3 // 3
+    _chk(load().adapt_gru_cell_f32(_ptr(acc_ih, torch.int32), _ptr(acc_hh, torch.int32), float(s_ih), float(s_hh),
+                                   _ptr(b_ih, torch.float32), _ptr(b_hh, torch.float32), _ptr(h_prev, torch.float32),
+                                   _ptr(h, torch.float32), _ptr(qh, torch.int8), float(s_h), bits, B, Hs, _stream(stream)))
+    return h, qh
+
+
+def adapt_rnn_cell_f32(acc_ih, acc_hh, s_ih: float, s_hh: float, bias, h, relu: bool = False, qh=None, s_h: float = 1.0,
+                       bits: int = 8, stream=None):
+    B, Hs = acc_ih.shape
+    _chk(load().adapt_rnn_cell_f32(_ptr(acc_ih, torch.int32), _ptr(acc_hh, torch.int32), float(s_ih), float(s_hh),
+                                   _ptr(bias, torch.float32), 1 if relu else 0, _ptr(h, torch.float32), _ptr(qh, torch.int8),
+                                   float(s_h), bits, B, Hs, _stream(stream)))
+    return h, qh
 
 
 ACT_NONE, ACT_RELU, ACT_TANH = 0, 1, 2

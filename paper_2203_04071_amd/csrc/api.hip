@@ -13,6 +13,7 @@
 #include "lut_lines.hpp"
 #include "lut_wide.hpp"
 #include "lut_rows.hpp"
+#include "lut_grouped.hpp"
 
 namespace {
 
@@ -291,6 +292,7 @@ struct Geometry {
     int sh, sw, ph, pw, dh, dw;
     int kstride, img_stride;
     int wt;                 // GEMM mode only: the weights are stored [K][N] instead of [N][K]
+    int groups;             // convolution only: 0 or 1 = ordinary; else N and Cin count one group's channels
 };
 
 // Run the rows kernel once per table image of the handle.
@@ -310,9 +312,10 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
              const LstmStep *lstm = nullptr) {
     const int bits = lut->bits;
     const long long Ktot = (long long)g.taps * g.Cin;
+    const int ngroups = g.groups > 1 ? g.groups : 1;
     if (g.M == 0 || g.N == 0) return ADAPT_OK;
     if (Ktot == 0) {
-        const size_t n = (size_t)g.M * g.N;
+        const size_t n = (size_t)g.M * g.N * ngroups;
         adapt::fill_u32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(reinterpret_cast<uint32_t *>(out), 0u, n);
         HIP_TRY(hipGetLastError());
         return ADAPT_OK;
@@ -324,9 +327,9 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
         if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
     }
     int NT = 16, MT = 1024;
-    auto groups = [&](int nt, int mt) { return (long long)((g.M + mt - 1) / mt) * ((g.N + nt - 1) / nt); };
-    while (MT > 64 && (MT / 2 >= g.M || (groups(NT, MT) < cu && Ktot / (adapt::ROWS_THREADS / (MT / 2)) >= 16))) MT /= 2;
-    if (groups(NT, MT) < cu && g.N > 8) NT = 8;
+    auto wgs = [&](int nt, int mt) { return (long long)((g.M + mt - 1) / mt) * ((g.N + nt - 1) / nt) * ngroups; };
+    while (MT > 64 && (MT / 2 >= g.M || (wgs(NT, MT) < cu && Ktot / (adapt::ROWS_THREADS / (MT / 2)) >= 16))) MT /= 2;
+    if ((wgs(NT, MT) < cu && g.N > 8) || (ngroups > 1 && g.N <= 8)) NT = 8;
     if (lstm) { NT = 8; MT = 64; }      // the cell epilogue sits in the split-K reduction of the 8-column variant
     const int KS = adapt::ROWS_THREADS / MT;
     const int Npad = prepacked ? prepacked_npad : ((g.N + NT - 1) / NT) * NT;
@@ -334,9 +337,9 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     uint32_t *wofs = nullptr;
     int rc = ADAPT_OK;
     if (!prepacked) {
-        HIP_TRY(hipMallocAsync((void **)&wofs, (size_t)Ktot * Npad * sizeof(uint32_t), s));
+        HIP_TRY(hipMallocAsync((void **)&wofs, (size_t)Ktot * Npad * ngroups * sizeof(uint32_t), s));
         const size_t pack_n = (size_t)Ktot * Npad;
-        adapt::pack_row_offsets_kernel<<<(unsigned)((pack_n + 255) / 256), 256, 0, s>>>(
+        adapt::pack_row_offsets_kernel<<<dim3((unsigned)((pack_n + 255) / 256), (unsigned)ngroups), 256, 0, s>>>(
             w, wofs, (int)Ktot, g.N, Npad, g.Cin, g.taps, g.wt ? (int)adapt::MODE_CONVT : g.mode, 1 << (bits - 1), (1 << bits) - 1,
             lut->rs * 2);
         hipError_t pe = hipGetLastError();
@@ -346,7 +349,7 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     adapt::RowsParams p;
     p.x = x; p.wofs = prepacked ? prepacked : wofs; p.out = out;
     p.img_bytes = lut->img_bytes;
-    p.M = g.M; p.N = g.N; p.Npad = Npad; p.mode = g.mode; p.Cin = g.Cin; p.taps = g.taps; p.kw = g.kw;
+    p.M = g.M; p.N = g.N; p.Npad = Npad; p.out_ch = g.N * ngroups; p.mode = g.mode; p.Cin = g.Cin; p.taps = g.taps; p.kw = g.kw;
     p.H = g.H; p.W = g.W; p.Wo = g.Wo; p.HoWo = g.HoWo;
     p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.dh = g.dh; p.dw = g.dw;
     p.kstride = g.kstride; p.img_stride = g.img_stride;
@@ -362,7 +365,7 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
         p.Hs = lstm->Hs; p.acc_ih = lstm->acc_ih; p.bias = lstm->bias; p.c = lstm->c; p.h = lstm->h; p.qh_next = lstm->qh_next;
         p.s_ih = lstm->s_ih; p.s_hh = lstm->s_hh; p.s_h = lstm->s_h; p.Qh = lstm->Qh;
     }
-    dim3 grid((unsigned)((g.M + MT - 1) / MT), (unsigned)(Npad / NT));
+    dim3 grid((unsigned)((g.M + MT - 1) / MT), (unsigned)(Npad / NT), (unsigned)ngroups);
     size_t lds = (size_t)lut->img_bytes;
     if (KS > 1 && (size_t)adapt::ROWS_THREADS * NT * 4 > lds) lds = (size_t)adapt::ROWS_THREADS * NT * 4;
     for (int half = 0; half <= lut->storage && rc == ADAPT_OK; ++half) {
@@ -378,9 +381,46 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     }
     if (rc == ADAPT_OK && io && io->deq && !fuse) {
         const size_t inner = g.mode == adapt::MODE_GEMM ? 1 : (size_t)g.HoWo;
-        rc = finish_inplace(out, (size_t)g.M * g.N, (size_t)g.N, inner, *io, s);
+        rc = finish_inplace(out, (size_t)g.M * g.N * ngroups, (size_t)g.N * ngroups, inner, *io, s);
     }
     return rc;
+}
+
+// Grouped convolution with fewer than 8 output channels per group (depthwise and its relatives): direct form
+int run_grouped(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *out, int N, int Cin, int H, int W, int Cout, int Ho,
+                int Wo, int kh, int kw, int sh, int sw, int ph, int pw, int dh, int dw, int groups, hipStream_t s) {
+    adapt::GroupedParams p;
+    p.x = x; p.w = w; p.out = out; p.img_bytes = lut->img_bytes;
+    p.Cin = Cin; p.H = H; p.W = W; p.Cout = Cout; p.Ho = Ho; p.Wo = Wo; p.kh = kh; p.kw = kw;
+    p.sh = sh; p.sw = sw; p.ph = ph; p.pw = pw; p.dh = dh; p.dw = dw;
+    p.cg = Cin / groups; p.og = Cout / groups;
+    p.hoff = 1 << (lut->bits - 1); p.mask = (1 << lut->bits) - 1; p.row_bytes = lut->rs * 2;
+    p.total = (size_t)N * Cout * Ho * Wo;
+    if (!p.total) return ADAPT_OK;
+    int cu = 256;
+    {
+        int dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
+    }
+    // one workgroup per compute unit at most (the table image fills its LDS), fewer when there is little to do
+    size_t blocks = (p.total + adapt::ROWS_THREADS * 4 - 1) / (adapt::ROWS_THREADS * 4);
+    if (blocks > (size_t)cu) blocks = (size_t)cu;
+    if (blocks < 1) blocks = 1;
+    const size_t lds = (size_t)lut->img_bytes;
+    static size_t configured[2] = {0, 0};
+    for (int half = 0; half <= lut->storage; ++half) {
+        p.img = lut->img_dev[half];
+        p.shift = half == 0 ? -1 : 16;
+        const bool sgn = (lut->storage == 0) || half == 1;
+        auto kern = sgn ? adapt::lut_grouped_kernel<true> : adapt::lut_grouped_kernel<false>;
+        if (lds > configured[sgn]) {
+            HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            configured[sgn] = lds;
+        }
+        kern<<<(unsigned)blocks, adapt::ROWS_THREADS, lds, s>>>(p);
+        HIP_TRY(hipGetLastError());
+    }
+    return ADAPT_OK;
 }
 
 
@@ -958,7 +998,6 @@ int adapt_approx_conv2d(const adapt_lut *lut, const int8_t *x_dev, const int8_t 
         pad_h < 0 || pad_w < 0 || dil_h < 1 || dil_w < 1 || groups < 1)
         return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_conv2d: bad dimension");
     if (Cin % groups || Cout % groups) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_conv2d: channels not divisible by groups");
-    if (groups != 1) return fail(ADAPT_ERR_UNSUPPORTED, "adapt_approx_conv2d: groups=%d (only 1 in this build)", groups);
     const long long Ho = ((long long)H + 2LL * pad_h - (long long)dil_h * (kh - 1) - 1) / stride_h + 1;
     const long long Wo = ((long long)W + 2LL * pad_w - (long long)dil_w * (kw - 1) - 1) / stride_w + 1;
     if ((long long)H + 2LL * pad_h - (long long)dil_h * (kh - 1) - 1 < 0 || (long long)W + 2LL * pad_w - (long long)dil_w * (kw - 1) - 1 < 0)
@@ -968,12 +1007,15 @@ int adapt_approx_conv2d(const adapt_lut *lut, const int8_t *x_dev, const int8_t 
     if ((long long)N * Cout * Ho * Wo > 0x7fffffffLL || (long long)N * Cin * H * W > 0x7fffffffLL ||
         (long long)N * Ho * Wo > 0x7fffffffLL || (long long)Cout * Cin * kh * kw > 0x7fffffffLL)
         return fail(ADAPT_ERR_UNSUPPORTED, "adapt_approx_conv2d: tensor with more than 2^31-1 elements");
+    if (groups > 1 && Cout / groups < 8)
+        return run_grouped(lut, x_dev, w_dev, acc_dev, N, Cin, H, W, Cout, (int)Ho, (int)Wo, kh, kw, stride_h, stride_w, pad_h, pad_w,
+                           dil_h, dil_w, groups, (hipStream_t)stream);
     Geometry g{};
-    g.mode = adapt::MODE_CONV; g.M = (int)(N * Ho * Wo); g.N = Cout; g.Cin = Cin; g.taps = kh * kw; g.kw = kw;
+    g.mode = adapt::MODE_CONV; g.M = (int)(N * Ho * Wo); g.N = Cout / groups; g.Cin = Cin / groups; g.taps = kh * kw; g.kw = kw;
     g.H = H; g.W = W; g.Wo = (int)Wo; g.HoWo = (int)(Ho * Wo);
     g.sh = stride_h; g.sw = stride_w; g.ph = pad_h; g.pw = pad_w; g.dh = dil_h; g.dw = dil_w;
-    g.kstride = H * W; g.img_stride = Cin * H * W;
-    if (g.M >= LINES_MIN_ROWS && Cin >= 4) {
+    g.kstride = H * W; g.img_stride = Cin * H * W; g.groups = groups;
+    if (groups == 1 && g.M >= LINES_MIN_ROWS && Cin >= 4) {
         const LinesShape q = lines_shape(1, lut->bits, Cout, Cin, kh, kw, lut->storage == 0);
         const long long xt_bytes = (long long)N * (H + 2LL * pad_h) * (W + 2LL * pad_w) * q.Cp;
         if (lines_fits(xt_bytes, q.dt_bytes, lut->storage))
@@ -1489,6 +1531,44 @@ int adapt_lstm_cell_q_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, 
     if (bits < 2 || bits > 8) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lstm_cell_q_f32: bits=%d not in [2,8]", bits);
     if (!(s_h > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lstm_cell_q_f32: scale must be > 0");
     return lstm_cell(acc_ih_dev, acc_hh_dev, s_ih, s_hh, bias_dev, c_dev, h_dev, qh_dev, s_h, bits, B, Hs, stream, "adapt_lstm_cell_q_f32");
+}
+
+static int cell_args(const char *who, const void *a, const void *b, const void *h, const int8_t *qh, float s_h, int bits, int B, int Hs,
+                     size_t *n) {
+    if (B < 0 || Hs < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: negative dimension", who);
+    *n = (size_t)B * Hs;
+    if (!*n) return ADAPT_OK;
+    if (!a || !b || !h) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
+    if (qh) {
+        if (bits < 2 || bits > 8) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bits=%d not in [2,8]", who, bits);
+        if (!(s_h > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: scale must be > 0", who);
+    }
+    return ADAPT_OK;
+}
+
+int adapt_gru_cell_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh, const float *b_ih_dev,
+                       const float *b_hh_dev, const float *h_prev_dev, float *h_dev, int8_t *qh_dev, float s_h, int bits, int B,
+                       int Hs, void *stream) {
+    size_t n = 0;
+    int rc = cell_args("adapt_gru_cell_f32", acc_ih_dev, acc_hh_dev, h_dev, qh_dev, s_h, bits, B, Hs, &n);
+    if (rc || !n) return rc;
+    if (!h_prev_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_gru_cell_f32: NULL pointer");
+    adapt::gru_cell_kernel<<<(unsigned)((n + adapt::EW_THREADS - 1) / adapt::EW_THREADS), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(
+        acc_ih_dev, acc_hh_dev, s_ih, s_hh, b_ih_dev, b_hh_dev, h_prev_dev, h_dev, B, Hs, qh_dev, s_h,
+        qh_dev ? (float)((1 << (bits - 1)) - 1) : 1.0f);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+int adapt_rnn_cell_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh, const float *bias_dev, int relu,
+                       float *h_dev, int8_t *qh_dev, float s_h, int bits, int B, int Hs, void *stream) {
+    size_t n = 0;
+    int rc = cell_args("adapt_rnn_cell_f32", acc_ih_dev, acc_hh_dev, h_dev, qh_dev, s_h, bits, B, Hs, &n);
+    if (rc || !n) return rc;
+    adapt::rnn_cell_kernel<<<(unsigned)((n + adapt::EW_THREADS - 1) / adapt::EW_THREADS), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(
+        acc_ih_dev, acc_hh_dev, s_ih, s_hh, bias_dev, relu, h_dev, B, Hs, qh_dev, s_h, qh_dev ? (float)((1 << (bits - 1)) - 1) : 1.0f);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
 }
 
 }  // extern "C"

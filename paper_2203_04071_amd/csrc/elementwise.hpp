@@ -306,4 +306,55 @@ __global__ __launch_bounds__(EW_THREADS) void lstm_cell_kernel(const int32_t *__
     if (qh) qh[i] = (int8_t)quant1(hn, s_h, Qh);      // the next step's operand, same quantiser as quantize_kernel
 }
 
+// GRU memory cell (Sec. III-B "RNN Layer"), gate order r, z, n along the 3 Hs axis; every operation a single
+// rounded fp32 operation in this order:
+//   gi = float(acc_ih) * s_ih (+ b_ih);  gh = float(acc_hh) * s_hh (+ b_hh)
+//   r = sigmoid(gi_r + gh_r);  z = sigmoid(gi_z + gh_z);  n = tanh(gi_n + r * gh_n);  h' = (1 - z) * n + z * h
+__global__ __launch_bounds__(EW_THREADS) void gru_cell_kernel(const int32_t *__restrict__ acc_ih, const int32_t *__restrict__ acc_hh,
+                                                              float s_ih, float s_hh, const float *__restrict__ b_ih,
+                                                              const float *__restrict__ b_hh, const float *h_prev, float *h, int B,
+                                                              int Hs, int8_t *__restrict__ qh, float s_h, float Qh) {
+    const size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (i >= (size_t)B * Hs) return;
+    const int b = (int)(i / Hs), j = (int)(i % Hs);
+    float gi[3], gh[3];
+#pragma unroll
+    for (int g = 0; g < 3; ++g) {
+        const size_t idx = (size_t)b * 3 * Hs + (size_t)g * Hs + j;
+        float u = (float)acc_ih[idx] * s_ih;
+        if (b_ih) u = u + b_ih[g * Hs + j];
+        float v = (float)acc_hh[idx] * s_hh;
+        if (b_hh) v = v + b_hh[g * Hs + j];
+        gi[g] = u;
+        gh[g] = v;
+    }
+    const float r = sigmoid_spec(gi[0] + gh[0]);
+    const float z = sigmoid_spec(gi[1] + gh[1]);
+    const float rn = r * gh[2];
+    const float n = tanh_spec(gi[2] + rn);
+    const float omz = 1.0f - z;
+    const float t0 = omz * n;
+    const float t1 = z * h_prev[i];
+    const float hn = t0 + t1;
+    h[i] = hn;
+    if (qh) qh[i] = (int8_t)quant1(hn, s_h, Qh);
+}
+
+// Plain recurrent cell: h' = act((float(acc_ih) * s_ih + float(acc_hh) * s_hh) + bias), act = tanh or ReLU
+__global__ __launch_bounds__(EW_THREADS) void rnn_cell_kernel(const int32_t *__restrict__ acc_ih, const int32_t *__restrict__ acc_hh,
+                                                              float s_ih, float s_hh, const float *__restrict__ bias, int relu,
+                                                              float *__restrict__ h, int B, int Hs, int8_t *__restrict__ qh, float s_h,
+                                                              float Qh) {
+    const size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (i >= (size_t)B * Hs) return;
+    const int j = (int)(i % Hs);
+    const float u = (float)acc_ih[i] * s_ih;
+    const float v = (float)acc_hh[i] * s_hh;
+    float s = u + v;
+    s = s + (bias ? bias[j] : 0.0f);
+    const float hn = relu ? (s > 0.0f ? s : 0.0f) : tanh_spec(s);
+    h[i] = hn;
+    if (qh) qh[i] = (int8_t)quant1(hn, s_h, Qh);
+}
+
 }  // namespace adapt

@@ -32,6 +32,8 @@ struct RowsParams {
     const uint16_t *img;    // table image: 2^b rows (one per weight) of RS = 2^b + 2 entries
     int img_bytes;          // multiple of 16
     int M, N, Npad;
+    int out_ch;             // channels of the output tensor: N, or groups * N for a grouped convolution (blockIdx.z = group:
+                            // x advanced by Cin channels, wofs by one [Ktot][Npad] block, outputs by N channels per group)
     int mode;
     int Cin;                // inner length per tap (GEMM: K)
     int taps, kw;           // kh * kw (GEMM: 1)
@@ -69,11 +71,14 @@ __device__ __forceinline__ uint32_t finish_sum(const RowsParams &p, uint32_t v, 
 }
 
 // weights -> byte offsets of their table rows, in the order the kernel walks K
+// (blockIdx.y = group of a grouped convolution: its N filters follow the previous group's, its block of offsets too)
 __global__ void pack_row_offsets_kernel(const int8_t *__restrict__ w, uint32_t *__restrict__ wofs, int Ktot,
                                         int N, int Npad, int Cin, int taps, int mode, int hoff, int mask,
                                         int row_bytes) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)Ktot * Npad) return;
+    w += (size_t)blockIdx.y * N * Ktot;
+    wofs += (size_t)blockIdx.y * Ktot * Npad;
     const int k = (int)(idx / Npad), n = (int)(idx % Npad);
     uint32_t v = 0;
     if (n < N) {
@@ -132,9 +137,12 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
     const int pix = mm - img * p.HoWo;
     const int oy = pix / p.Wo;
     const int ox = pix - oy * p.Wo;
-    const int8_t *xb = p.x + (size_t)img * p.img_stride;
+    const int grp = blockIdx.z;
+    const int8_t *xb = p.x + (size_t)img * p.img_stride + (size_t)grp * p.Cin * p.kstride;
 
     const int Ktot = p.taps * p.Cin;
+    const uint32_t *wofs = p.wofs + (size_t)grp * Ktot * p.Npad;
+    const int ch0 = grp * p.N;              // first output channel of the group
     const int kc = (Ktot + p.KS - 1) / p.KS;
     int k = ks * kc;
     const int k_end = min(Ktot, k + kc);
@@ -166,7 +174,7 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
                     for (int bq = 0; bq < 4; ++bq) {
                         const int a = (int)(int8_t)(cur[d] >> (8 * bq));
                         const uint32_t a2 = (uint32_t)(((a + p.hoff) & p.mask) << 1);
-                        const uint32_t *w1 = p.wofs + (size_t)(k + 4 * d + bq) * p.Npad + n0;
+                        const uint32_t *w1 = wofs + (size_t)(k + 4 * d + bq) * p.Npad + n0;
 #pragma unroll
                         for (int n = 0; n < NT; ++n) acc[n] += lds_entry<SIGNED>(smem, w1[n] + a2);
                     }
@@ -196,7 +204,7 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
         }
         const int fill2 = (p.mode == MODE_CONVT) ? p.a_skip2 : p.a_zero2;
         const int8_t *xp = xb + (valid ? base : 0) + (size_t)c0 * p.kstride;
-        const uint32_t *wr = p.wofs + (size_t)k * p.Npad + n0;
+        const uint32_t *wr = wofs + (size_t)k * p.Npad + n0;
         int c = 0;
         for (; c + 4 <= cnt; c += 4) {
             uint32_t a2[4];
@@ -224,12 +232,12 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
 
     if (p.KS == 1) {
         if (mvalid) {
-            int32_t *o = p.out + (size_t)img * p.N * p.HoWo + pix;
+            int32_t *o = p.out + (size_t)img * p.out_ch * p.HoWo + pix;
 #pragma unroll
             for (int n = 0; n < NT; ++n) {
                 if (n0 + n < p.N) {
-                    int32_t *q = o + (size_t)(n0 + n) * p.HoWo;
-                    if (p.shift < 0) *q = (int32_t)finish_sum(p, acc[n], n0 + n);
+                    int32_t *q = o + (size_t)(ch0 + n0 + n) * p.HoWo;
+                    if (p.shift < 0) *q = (int32_t)finish_sum(p, acc[n], ch0 + n0 + n);
                     else *q = (int32_t)((uint32_t)*q + (acc[n] << p.shift));
                 }
             }
@@ -283,8 +291,8 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
         uint32_t s = 0;
         for (int j = 0; j < p.KS; ++j) s += red[((size_t)j * NT + n) * p.MT + r];
         const int img2 = m2 / p.HoWo, pix2 = m2 - img2 * p.HoWo;
-        int32_t *q = p.out + (size_t)img2 * p.N * p.HoWo + (size_t)(n0 + n) * p.HoWo + pix2;
-        if (p.shift < 0) *q = (int32_t)finish_sum(p, s, n0 + n);
+        int32_t *q = p.out + (size_t)img2 * p.out_ch * p.HoWo + (size_t)(ch0 + n0 + n) * p.HoWo + pix2;
+        if (p.shift < 0) *q = (int32_t)finish_sum(p, s, ch0 + n0 + n);
         else *q = (int32_t)((uint32_t)*q + (s << p.shift));
     }
 }

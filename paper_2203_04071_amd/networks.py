@@ -176,6 +176,82 @@ class LSTM:
         return dict(hs=hs, c=c, acc_ih=acc_ih, acc_hh_last=acc_last, s_x=self.s_x, s_h=s_h)
 
 
+class Recurrent:
+    """Single-layer GRU ("gru") or plain tanh recurrent layer ("rnn") (Sec. III-B "RNN Layer"): the input products of all
+    time steps as one long table product, then per step the hidden-state product (pre-packed row offsets) and the cell
+    kernel, which also writes the quantised h that the next step multiplies."""
+
+    def __init__(self, cfg, kind, device="cuda"):
+        self.kind = kind
+        self.gates = {"gru": 3, "rnn": 1}[kind]
+        self.bits = cfg["bits"]
+        self.lut = B.Lut(cfg["lut"], self.bits)
+        self.q_wih, self.s_wih = quantize_weights(torch.from_numpy(cfg["w_ih"]).to(device), self.bits)
+        self.q_whh, self.s_whh = quantize_weights(torch.from_numpy(cfg["w_hh"]).to(device), self.bits)
+        self.p_wih = B.adapt_weights_pack_linear(self.lut, self.q_wih)
+        self.p_whh = B.adapt_weights_pack_linear(self.lut, self.q_whh)
+        if kind == "gru":
+            self.b_ih = torch.from_numpy(cfg["b_ih"]).to(device)
+            self.b_hh = torch.from_numpy(cfg["b_hh"]).to(device)
+        else:
+            self.bias = torch.from_numpy(cfg["bias"]).to(device)
+        self.Hs = cfg["w_hh"].shape[1]
+        self.s_x = None
+
+    def forward(self, x):
+        bits, G = self.bits, self.gates
+        T, Bn, I = x.shape
+        Q = (1 << (bits - 1)) - 1
+        if self.s_x is None:
+            self.s_x = calibrated_scale(x, bits)          # over the whole [T, B, I] input
+        s_h = _f(1.0) / _f(Q)
+        qx = B.adapt_quantize_f32(x, self.s_x, bits).view(T * Bn, I)
+        acc_ih = B.adapt_approx_linear_packed(self.p_wih, qx).view(T, Bn, G * self.Hs)
+        hs = torch.empty((T, Bn, self.Hs), dtype=torch.float32, device=x.device)
+        h = torch.zeros((Bn, self.Hs), dtype=torch.float32, device=x.device)
+        qh = torch.empty((Bn, self.Hs), dtype=torch.int8, device=x.device)
+        acc_hh = torch.empty((Bn, G * self.Hs), dtype=torch.int32, device=x.device)
+        s_ih = _f(self.s_x) * _f(self.s_wih)
+        s_hh = _f(s_h) * _f(self.s_whh)
+        B.adapt_quantize_f32(h, s_h, bits, out=qh)
+        for t in range(T):
+            B.adapt_approx_linear_packed(self.p_whh, qh, out=acc_hh)
+            if self.kind == "gru":
+                B.adapt_gru_cell_f32(acc_ih[t], acc_hh, s_ih, s_hh, self.b_ih, self.b_hh, h, hs[t], qh, s_h, bits)
+            else:
+                B.adapt_rnn_cell_f32(acc_ih[t], acc_hh, s_ih, s_hh, self.bias, hs[t], False, qh, s_h, bits)
+            h = hs[t]
+        return dict(hs=hs, acc_ih=acc_ih, acc_hh_last=acc_hh, s_x=self.s_x, s_h=s_h)
+
+
+class SeparableConv:
+    """Separable convolution (Sec. III-B, eq. (1)): depthwise table-lookup convolution (groups = Cin), then the
+    pointwise 1x1 convolution as a fused layer call."""
+
+    def __init__(self, cfg, device="cuda"):
+        self.bits = cfg["bits"]
+        self.lut = B.Lut(cfg["lut"], self.bits)
+        self.q_dw, self.s_dw = quantize_weights(torch.from_numpy(cfg["w_dw"]).to(device), self.bits)
+        self.q_pw, self.s_pw = quantize_weights(torch.from_numpy(cfg["w_pw"]).to(device), self.bits)
+        self.p_pw = B.adapt_weights_pack_conv2d(self.lut, self.q_pw)
+        self.stride, self.pad = cfg["stride"], cfg["pad"]
+        self.scales = None
+
+    def forward(self, x):
+        bits = self.bits
+        cin = x.shape[1]
+        s_x = self.scales[0] if self.scales is not None else calibrated_scale(x, bits)
+        qx = B.adapt_quantize_f32(x, s_x, bits)
+        acc_dw = B.adapt_approx_conv2d(self.lut, qx, self.q_dw, (self.stride, self.stride), (self.pad, self.pad), groups=cin)
+        n, c, h, w = acc_dw.shape
+        y = B.adapt_dequant_i32(acc_dw, _f(s_x) * _f(self.s_dw), n, c, h * w)
+        s_y = self.scales[1] if self.scales is not None else calibrated_scale(y, bits)
+        out = B.adapt_conv2d_layer_f32(self.p_pw, y, s_y, _f(s_y) * _f(self.s_pw))
+        if self.scales is None:
+            self.scales = [s_x, s_y]
+        return dict(out=out, y=y, acc_dw=acc_dw, scales=[s_x, s_y])
+
+
 class DCGAN:
     def __init__(self, cfg, device="cuda"):
         self.bits = cfg["bits"]

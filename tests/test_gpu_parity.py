@@ -141,6 +141,54 @@ def test_lstm_cell_bit_exact(B, Bn, Hs):
         assert (host(qd) == orc.quantize(h_w, s_h, 7)).all()
 
 
+@pytest.mark.parametrize("Bn,Hs", [(1, 1), (3, 17), (64, 512)])
+def test_gru_and_rnn_cells_bit_exact(B, Bn, Hs):
+    rng = np.random.default_rng(7 + Bn + Hs)
+    a1 = rng.integers(-300000, 300000, size=(Bn, 3 * Hs)).astype(np.int32)
+    a2 = rng.integers(-300000, 300000, size=(Bn, 3 * Hs)).astype(np.int32)
+    b1 = rng.standard_normal(3 * Hs).astype(np.float32)
+    b2 = rng.standard_normal(3 * Hs).astype(np.float32)
+    h = rng.uniform(-1, 1, (Bn, Hs)).astype(np.float32)
+    s1, s2 = np.float32(1.3e-5), np.float32(2.1e-5)
+    s_h = np.float32(1.0) / np.float32(63)
+    for bi, bh in ((b1, b2), (None, b2), (b1, None), (None, None)):
+        want = orc.gru_cell(a1, a2, s1, s2, bi, bh, h)
+        hd = torch.empty((Bn, Hs), dtype=torch.float32, device="cuda")
+        qd = torch.empty((Bn, Hs), dtype=torch.int8, device="cuda")
+        B.adapt_gru_cell_f32(dev(a1), dev(a2), s1, s2, dev(bi) if bi is not None else None, dev(bh) if bh is not None else None,
+                             dev(h), hd, qd, s_h, 7)
+        assert bits_equal(host(hd), want)
+        assert (host(qd) == orc.quantize(want, s_h, 7)).all()
+        hin = dev(h)                                            # in place, no quantised output
+        B.adapt_gru_cell_f32(dev(a1), dev(a2), s1, s2, dev(bi) if bi is not None else None, dev(bh) if bh is not None else None,
+                             hin, hin)
+        assert bits_equal(host(hin), want)
+    r1, r2, rb = a1[:, :Hs].copy(), a2[:, :Hs].copy(), b1[:Hs].copy()
+    for relu in (False, True):
+        for b in (rb, None):
+            want = orc.rnn_cell(r1, r2, s1, s2, b, relu=relu)
+            hd = torch.empty((Bn, Hs), dtype=torch.float32, device="cuda")
+            qd = torch.empty((Bn, Hs), dtype=torch.int8, device="cuda")
+            B.adapt_rnn_cell_f32(dev(r1), dev(r2), s1, s2, dev(b) if b is not None else None, hd, relu, qd, s_h, 7)
+            assert bits_equal(host(hd), want)
+            assert (host(qd) == orc.quantize(want, s_h, 7)).all()
+
+
+@pytest.mark.parametrize("kind", ["gru", "rnn"])
+@pytest.mark.parametrize("bits", [7, 8])
+def test_recurrent_layers_match_oracle(B, kind, bits):
+    """GRU / plain recurrent layer end to end (quantise, input products, per-step hidden products, cells)."""
+    from paper_2203_04071_amd import networks as gnet
+    cfg = wl.recurrent_workload(kind, seq=12, batch=16, isz=96, hsz=72, bits=bits)
+    want = onet.gru(cfg, threads=4) if kind == "gru" else onet.rnn(cfg, threads=4)
+    net = gnet.Recurrent(cfg, kind)
+    got = net.forward(dev(cfg["x"]))
+    assert got["s_x"] == want["s_x"]
+    assert (host(got["acc_ih"]) == want["acc_ih"]).all()
+    assert (host(got["acc_hh_last"]) == want["acc_hh_last"]).all()
+    assert bits_equal(host(got["hs"]), want["hs"])
+
+
 # ------------------------------------------------------------------ table-lookup linear layer
 
 LINEAR_SHAPES = [
@@ -221,8 +269,8 @@ def test_errors_on_device_handles(B):
         B.adapt_approx_conv2d(L, x, w1, out=dummy)           # filter larger than the input
     assert e.value.code == -1
     with pytest.raises(B.AdaptError) as e:
-        B.adapt_approx_conv2d(L, x, w, groups=2, out=dummy)
-    assert e.value.code == -2
+        B.adapt_approx_conv2d(L, x, w, groups=3, out=dummy)         # channels not divisible by groups
+    assert e.value.code == -1
     with pytest.raises(B.AdaptError):
         B.adapt_quantize_f32(torch.zeros(4, device="cuda"), -1.0, 8)
 
@@ -256,6 +304,59 @@ def test_conv2d_bit_exact(B, bits, case):
     got = host(B.adapt_approx_conv2d(L, dev(x), dev(w), (sh, sw), (ph, pw), (dh, dw)))
     want = orc.approx_conv2d(lut, bits, x, w, (sh, sw), (ph, pw), (dh, dw), threads=4)
     assert got.shape == want.shape and (got == want).all()
+
+
+GROUPED_CASES = [
+    # N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, groups
+    (2, 6, 5, 5, 6, 3, 3, 1, 1, 1, 1, 1, 1, 6),            # depthwise
+    (3, 32, 16, 16, 32, 3, 3, 1, 1, 1, 1, 1, 1, 32),       # depthwise, several workgroups
+    (2, 24, 15, 13, 24, 5, 5, 2, 2, 2, 2, 1, 1, 24),       # depthwise 5x5 stride 2, ragged
+    (2, 8, 9, 9, 16, 3, 3, 1, 1, 1, 1, 1, 1, 8),           # channel multiplier 2
+    (1, 4, 8, 8, 8, 3, 3, 1, 1, 2, 2, 2, 2, 2),            # 2 groups of 2 -> 4, dilated
+    (2, 12, 7, 7, 9, 3, 3, 1, 1, 1, 1, 1, 1, 3),           # 3 groups of 4 -> 3
+    (2, 32, 12, 12, 64, 3, 3, 1, 1, 1, 1, 1, 1, 4),        # 4 groups of 8 -> 16: rows kernel, one launch over the groups
+    (1, 48, 10, 10, 40, 3, 3, 2, 2, 1, 1, 1, 1, 2),        # 2 groups of 24 -> 20 (ragged channel tile)
+    (3, 16, 33, 33, 16, 1, 1, 1, 1, 0, 0, 1, 1, 2),        # 1x1 grouped, 8 -> 8 per group
+]
+
+
+@pytest.mark.parametrize("bits", [6, 8])
+@pytest.mark.parametrize("case", GROUPED_CASES)
+def test_grouped_conv2d_bit_exact(B, bits, case):
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, g = case
+    rng = np.random.default_rng(bits + sum(case))
+    x = wl.random_i8(rng, (N, Cin, H, W), bits, "gauss")
+    w = wl.random_i8(rng, (Cout, Cin // g, kh, kw), bits, "gauss")
+    lut = wl.make_lut(bits)
+    got = host(B.adapt_approx_conv2d(B.Lut(lut, bits), dev(x), dev(w), (sh, sw), (ph, pw), (dh, dw), groups=g))
+    want = orc.approx_conv2d(lut, bits, x, w, (sh, sw), (ph, pw), (dh, dw), g, threads=4)
+    assert got.shape == want.shape and (got == want).all()
+
+
+def test_grouped_conv2d_two_pass_table(B):
+    """Entries beyond int16 (two table images, two passes) through both grouped paths."""
+    rng = np.random.default_rng(77)
+    lut = (rng.integers(-2**20, 2**20, size=(64, 64))).astype(np.int32)
+    for (cin, cout, g) in ((8, 8, 8), (16, 32, 2)):
+        x = wl.random_i8(rng, (2, cin, 9, 9), 6)
+        w = wl.random_i8(rng, (cout, cin // g, 3, 3), 6)
+        got = host(B.adapt_approx_conv2d(B.Lut(lut, 6), dev(x), dev(w), (1, 1), (1, 1), groups=g))
+        assert (got == orc.approx_conv2d(lut, 6, x, w, (1, 1), (1, 1), (1, 1), g, threads=4)).all()
+
+
+def test_separable_convolution_matches_oracle(B):
+    """Eq. (1): depthwise then pointwise, each an approximate layer; calibrated and frozen-scale passes."""
+    from paper_2203_04071_amd import networks as gnet
+    cfg = wl.separable_workload()
+    want = onet.separable_conv(cfg, threads=4)
+    net = gnet.SeparableConv(cfg)
+    got = net.forward(dev(cfg["x"]))
+    assert [float(v) for v in got["scales"]] == [float(v) for v in want["scales"]]
+    assert (host(got["acc_dw"]) == want["acc_dw"]).all()
+    assert bits_equal(host(got["y"]), want["y"])
+    assert bits_equal(host(got["out"]), want["out"])
+    again = net.forward(dev(cfg["x"]))
+    assert bits_equal(host(again["out"]), want["out"])
 
 
 def test_conv2d_padding_is_looked_up(B):
