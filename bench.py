@@ -110,6 +110,21 @@ def build_step(cfg_id, bits, torch, B, gnet, wl, eager=False):
         net.forward(z)
         step = _graph_step(gnet, net, z, eager)
         return step, None, gnet.lut_macs_dcgan(256, c["plan"]), f"config5: DCGAN-style generator, batch 256, {bits}-bit table", net
+    if cfg_id == 6:     # beyond the five baseline configurations: separable convolution block (Sec. III-B, eq. (1))
+        c = wl.separable_workload(batch=32, cin=128, cout=128, hw=32)
+        net = gnet.SeparableConv(c)
+        x = dev(c["x"])
+        net.forward(x)
+        step = _graph_step(gnet, net, x, eager)
+        macs = wl.lut_macs_conv2d(32, 128, 32, 32, 128, 3, 3, 1, 1, 1, 1, groups=128) + wl.lut_macs_conv2d(32, 128, 32, 32, 128, 1, 1, 1, 1, 0, 0)
+        return step, None, macs, "extra: separable convolution 3x3 depthwise + 1x1, batch 32, 128->128 ch, 32x32, 8-bit table", net
+    if cfg_id == 7:     # GRU layer at the size of the LSTM configuration (Sec. III-B "RNN Layer")
+        c = wl.recurrent_workload("gru", seq=100, batch=64, isz=512, hsz=512, bits=7)
+        net = gnet.Recurrent(c, "gru")
+        x = dev(c["x"])
+        net.forward(x)
+        step = _graph_step(gnet, net, x, eager)
+        return step, None, 100 * 64 * 3 * 512 * (512 + 512), "extra: GRU 512/512, seq 100, batch 64, 7-bit table", net
     raise SystemExit(f"unknown config {cfg_id}")
 
 
@@ -156,6 +171,19 @@ def cpu_baseline(cfg_id, bits, wl):
         onet.lstm(c, threads=th, steps=10)
         dt = time.perf_counter() - t0
         return dict(value=134217728 * 10 / dt, unit="LUT-MAC/s", cores=th, kind="oracle", sample="first 10 of 100 time steps")
+    if cfg_id == 6:
+        c = wl.separable_workload(batch=8, cin=128, cout=128, hw=32)
+        t0 = time.perf_counter()
+        onet.separable_conv(c, threads=th)
+        dt = time.perf_counter() - t0
+        macs = wl.lut_macs_conv2d(8, 128, 32, 32, 128, 3, 3, 1, 1, 1, 1, groups=128) + wl.lut_macs_conv2d(8, 128, 32, 32, 128, 1, 1, 1, 1, 0, 0)
+        return dict(value=macs / dt, unit="LUT-MAC/s", cores=th, kind="oracle", sample="8 of 32 images, one pass incl. calibration")
+    if cfg_id == 7:
+        c = wl.recurrent_workload("gru", seq=100, batch=64, isz=512, hsz=512, bits=7)
+        t0 = time.perf_counter()
+        onet.gru(c, threads=th, steps=10)
+        dt = time.perf_counter() - t0
+        return dict(value=64 * 3 * 512 * 1024 * 10 / dt, unit="LUT-MAC/s", cores=th, kind="oracle", sample="first 10 of 100 time steps")
     c = wl.config5(bits=bits, batch=32)
     t0 = time.perf_counter()
     onet.dcgan(c, threads=th)
@@ -168,7 +196,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--config", type=int, default=2, help="1-5: the baseline configurations (default 2, the one the metric is quoted on); "
+                    "6: separable convolution block, 7: GRU layer (rows beyond the baseline, not bench lines of record)")
     ap.add_argument("--bits", type=int, default=8, help="table bits for config 5 (6 or 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="network configurations: launch kernel by kernel instead of replaying a HIP graph")

@@ -402,20 +402,55 @@ int run_grouped(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t 
         int dev = 0;
         if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
     }
-    // one workgroup per compute unit at most (the table image fills its LDS), fewer when there is little to do
-    size_t blocks = (p.total + adapt::ROWS_THREADS * 4 - 1) / (adapt::ROWS_THREADS * 4);
-    if (blocks > (size_t)cu) blocks = (size_t)cu;
-    if (blocks < 1) blocks = 1;
-    const size_t lds = (size_t)lut->img_bytes;
-    static size_t configured[2] = {0, 0};
+    // tiled form: the input region of a tile and the tap words of its groups sit in LDS next to the table
+    const int taps = kh * kw;
+    const long long Wr = (long long)(Wo - 1) * sw + (long long)(kw - 1) * dw + 1;
+    const long long rows_min = (long long)(kh - 1) * dh + 1;
+    const long long cap = (long long)adapt::GROUPED_PF * adapt::ROWS_THREADS;
+    const long long wgroup = (long long)p.og * p.cg * taps;             // tap words of one group
+    const size_t wl_bytes = (size_t)adapt::ROWS_THREADS * 4;
+    const bool tiled = wgroup <= adapt::ROWS_THREADS && p.cg * rows_min * Wr <= cap &&
+                       (size_t)lut->img_bytes + wl_bytes + (size_t)cap <= 160 * 1024;
+    size_t blocks, lds;
+    if (tiled) {
+        // rows per tile: as many as the region buffer holds for one group; then as many groups as still fit; both
+        // reduced again while the tiles would not cover the chip twice
+        long long ro = (cap / ((long long)p.cg * Wr) - rows_min) / sh + 1;
+        if (ro > Ho) ro = Ho;
+        auto rows_in = [&](long long r) { return (r - 1) * sh + rows_min; };
+        long long gt = cap / ((long long)p.cg * rows_in(ro) * Wr);
+        if (gt > adapt::ROWS_THREADS / wgroup) gt = adapt::ROWS_THREADS / wgroup;
+        if (gt > groups) gt = groups;
+        if (gt < 1) gt = 1;
+        auto tiles = [&](long long r, long long g) { return (long long)N * ((groups + g - 1) / g) * ((Ho + r - 1) / r); };
+        while (gt > 1 && tiles(ro, gt) < 2LL * cu) gt = (gt + 1) / 2;
+        while (ro > 1 && tiles(ro, gt) < 2LL * cu) ro = (ro + 1) / 2;
+        if (tiles(ro, gt) > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "adapt_approx_conv2d: too many tiles");
+        p.gt = (int)gt;
+        p.ro = (int)ro; p.n_chunks = (int)((Ho + ro - 1) / ro);
+        p.rows_in = (int)rows_in(ro); p.Wr = (int)Wr;
+        p.tile_elems = (int)gt * p.cg * p.rows_in * p.Wr;
+        p.wl_bytes = (int)wl_bytes;
+        p.ntiles = (int)tiles(ro, gt);
+        blocks = (size_t)p.ntiles < (size_t)cu ? (size_t)p.ntiles : (size_t)cu;
+        lds = (size_t)lut->img_bytes + wl_bytes + (size_t)((p.tile_elems + 15) / 16 * 16);
+    } else {
+        // one workgroup per compute unit at most (the table image fills its LDS), fewer when there is little to do
+        p.gt = p.ro = p.n_chunks = p.rows_in = p.Wr = p.tile_elems = p.wl_bytes = p.ntiles = 0;
+        blocks = (p.total + adapt::ROWS_THREADS * 4 - 1) / (adapt::ROWS_THREADS * 4);
+        if (blocks > (size_t)cu) blocks = (size_t)cu;
+        lds = (size_t)lut->img_bytes;
+    }
+    static size_t configured[2][2] = {{0, 0}, {0, 0}};
     for (int half = 0; half <= lut->storage; ++half) {
         p.img = lut->img_dev[half];
         p.shift = half == 0 ? -1 : 16;
         const bool sgn = (lut->storage == 0) || half == 1;
-        auto kern = sgn ? adapt::lut_grouped_kernel<true> : adapt::lut_grouped_kernel<false>;
-        if (lds > configured[sgn]) {
+        auto kern = tiled ? (sgn ? adapt::lut_grouped_tiled_kernel<true> : adapt::lut_grouped_tiled_kernel<false>)
+                          : (sgn ? adapt::lut_grouped_kernel<true> : adapt::lut_grouped_kernel<false>);
+        if (lds > configured[tiled][sgn]) {
             HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            configured[sgn] = lds;
+            configured[tiled][sgn] = lds;
         }
         kern<<<(unsigned)blocks, adapt::ROWS_THREADS, lds, s>>>(p);
         HIP_TRY(hipGetLastError());

@@ -119,7 +119,7 @@ def compile_to_asm(out_path):
         raise RuntimeError("hipcc -S failed:\n" + r.stdout + r.stderr)
 
 
-def check_build(pattern='lut_lines_(fast_|wide_)?kernel'):
+def check_build(pattern='lut_lines_(fast_|wide_)?kernel|lut_grouped_tiled_kernel'):
     """Number of violations in a fresh compilation of the library's device code."""
     with tempfile.TemporaryDirectory() as d:
         path = os.path.join(d, "api.s")

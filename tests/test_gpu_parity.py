@@ -317,6 +317,9 @@ GROUPED_CASES = [
     (2, 32, 12, 12, 64, 3, 3, 1, 1, 1, 1, 1, 1, 4),        # 4 groups of 8 -> 16: rows kernel, one launch over the groups
     (1, 48, 10, 10, 40, 3, 3, 2, 2, 1, 1, 1, 1, 2),        # 2 groups of 24 -> 20 (ragged channel tile)
     (3, 16, 33, 33, 16, 1, 1, 1, 1, 0, 0, 1, 1, 2),        # 1x1 grouped, 8 -> 8 per group
+    (1, 8, 6, 210, 4, 5, 5, 1, 1, 2, 2, 1, 1, 2),          # input region of one output row too large to stage: direct form
+    (2, 3, 70, 70, 3, 3, 3, 1, 1, 1, 1, 1, 1, 3),          # depthwise, planes larger than a tile: several row chunks
+    (1, 64, 8, 8, 64, 3, 3, 1, 1, 1, 1, 1, 1, 64),         # small planes, many channels
 ]
 
 
