@@ -311,3 +311,76 @@ def rnn_cell(acc_ih, acc_hh, s_ih, s_hh, bias, relu=False):
     lib().orc_rnn_cell_f32(_p(acc_ih), _p(acc_hh), ctypes.c_float(float(s_ih)), ctypes.c_float(float(s_hh)),
                            _p(b) if b is not None else None, ctypes.c_int(1 if relu else 0), _p(out), L(B), L(Hs))
     return out
+
+
+# ---- operands wider than 8 bits, multipliers as functions (Sec. III-C; 12-bit unit of Sec. V)
+
+FUNC_EXACT, FUNC_TRUNC, FUNC_MITCHELL = 0, 1, 2
+
+
+def _i16(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.int16
+    return a
+
+
+def mul_func(kind, param, a, w) -> int:
+    f = lib().orc_mul_func
+    f.restype = ctypes.c_int32
+    return int(f(ctypes.c_int(kind), ctypes.c_int(param), ctypes.c_int(int(a)), ctypes.c_int(int(w))))
+
+
+def table_from_func(kind, param, bits) -> np.ndarray:
+    n = 1 << bits
+    t = np.empty((n, n), dtype=np.int32)
+    _check(lib().orc_table_from_func(ctypes.c_int(kind), ctypes.c_int(param), ctypes.c_int(bits), _p(t)), "table_from_func")
+    return t
+
+
+def approx_linear_i16(lut, bits, A, W, threads: int = 1) -> np.ndarray:
+    A, W = _i16(A), _i16(W)
+    M, K = A.shape
+    N, K2 = W.shape
+    assert K == K2
+    t = np.ascontiguousarray(lut, dtype=np.int32)
+    assert t.shape == (1 << bits, 1 << bits)
+    acc = np.empty((M, N), dtype=np.int32)
+    _check(lib().orc_approx_linear_i16(_p(t), ctypes.c_int(bits), _p(A), _p(W), _p(acc), L(M), L(K), L(N),
+                                       ctypes.c_int(threads)), "approx_linear_i16")
+    return acc
+
+
+def approx_linear_func_i16(kind, param, bits, A, W, threads: int = 1) -> np.ndarray:
+    A, W = _i16(A), _i16(W)
+    M, K = A.shape
+    N, K2 = W.shape
+    assert K == K2
+    acc = np.empty((M, N), dtype=np.int32)
+    _check(lib().orc_approx_linear_func_i16(ctypes.c_int(kind), ctypes.c_int(param), ctypes.c_int(bits), _p(A), _p(W),
+                                            _p(acc), L(M), L(K), L(N), ctypes.c_int(threads)), "approx_linear_func_i16")
+    return acc
+
+
+def approx_conv2d_i16(bits, x, w, lut=None, func=None, stride=(1, 1), pad=(0, 0), dil=(1, 1), threads: int = 1) -> np.ndarray:
+    """Table form (lut given) or function form (func = (kind, param))."""
+    x, w = _i16(x), _i16(w)
+    N, Cin, H, W_ = x.shape
+    Cout, Cin2, kh, kw = w.shape
+    assert Cin == Cin2 and (lut is None) != (func is None)
+    Ho, Wo = conv_out_hw(H, W_, kh, kw, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1])
+    acc = np.empty((N, Cout, Ho, Wo), dtype=np.int32)
+    t = np.ascontiguousarray(lut, dtype=np.int32) if lut is not None else None
+    kind, param = func if func is not None else (0, 0)
+    _check(lib().orc_approx_conv2d_i16(_p(t) if t is not None else None, ctypes.c_int(kind), ctypes.c_int(param),
+                                       ctypes.c_int(bits), _p(x), _p(w), _p(acc), L(N), L(Cin), L(H), L(W_), L(Cout), L(kh),
+                                       L(kw), L(stride[0]), L(stride[1]), L(pad[0]), L(pad[1]), L(dil[0]), L(dil[1]),
+                                       ctypes.c_int(threads)), "approx_conv2d_i16")
+    return acc
+
+
+def quantize_i16(x, scale, bits) -> np.ndarray:
+    x = _f32(x)
+    q = np.empty(x.shape, dtype=np.int16)
+    _check(lib().orc_quantize_i16_f32(_p(x), _p(q), ctypes.c_size_t(x.size), ctypes.c_float(float(scale)),
+                                      ctypes.c_int(bits)), "quantize_i16")
+    return q

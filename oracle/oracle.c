@@ -501,3 +501,138 @@ void orc_rnn_cell_f32(const int32_t *acc_ih, const int32_t *acc_hh, float s_ih, 
             h_out[idx] = relu ? (s > 0.0f ? s : 0.0f) : orc_tanh_f32(s);
         }
 }
+
+/* ===========================================================================
+ * Operands wider than 8 bits and multipliers given as functions
+ * (Sec. III-C "Framework operation": a table per multiplier, or - for large
+ * bitwidths - the multiplier described as a function, "both a 1-1
+ * representation" of the unit; Sec. V evaluates a 12-bit unit).
+ * Operands are int16 in [-H, H-1], H = 2^(b-1); same table index convention
+ * and the same sums as above.
+ * ========================================================================= */
+
+static int in_range16(const int16_t *p, size_t n, int bits) {
+    const int h = 1 << (bits - 1);
+    for (size_t i = 0; i < n; ++i)
+        if (p[i] < -h || p[i] > h - 1) return 0;
+    return 1;
+}
+
+/* Multipliers as functions of two signed operands.  kind 0: exact product.
+ * kind 1: both operands lose their `param` low bits (arithmetic shift, i.e. floor) before an exact multiply, the
+ *         product is shifted back: ((a >> t) * (w >> t)) << 2t.
+ * kind 2: Mitchell's logarithmic multiplier on the magnitudes (sign restored afterwards): with a = 2^ka + xa,
+ *         w = 2^kw + xw (ka, kw the positions of the leading ones), s = xa 2^kw + xw 2^ka:
+ *         |a||w| ~ 2^(ka+kw) + s  if s < 2^(ka+kw),  else 2 s;   0 if an operand is 0.   (`param` unused.) */
+int32_t orc_mul_func(int kind, int param, int a, int w) {
+    if (kind == 0) return (int32_t)(a * w);
+    if (kind == 1) {
+        const int t = param;
+        const int32_t pa = a >> t, pw = w >> t;      /* arithmetic shifts of negative values: floor */
+        return (int32_t)((uint32_t)(pa * pw) << (2 * t));
+    }
+    const int neg = (a < 0) != (w < 0);
+    uint32_t ma = (uint32_t)(a < 0 ? -a : a), mw = (uint32_t)(w < 0 ? -w : w);
+    if (ma == 0 || mw == 0) return 0;
+    int ka = 0, kw = 0;
+    while ((ma >> (ka + 1)) != 0) ++ka;
+    while ((mw >> (kw + 1)) != 0) ++kw;
+    const uint32_t xa = ma - (1u << ka), xw = mw - (1u << kw);
+    const uint32_t s = (xa << kw) + (xw << ka);
+    const uint32_t one = 1u << (ka + kw);
+    const uint32_t p = s < one ? one + s : 2u * s;
+    return neg ? -(int32_t)p : (int32_t)p;
+}
+
+/* The table of a function-described multiplier (the table generator of Sec. III-C): T[(a+H) 2^b + (w+H)]. */
+int orc_table_from_func(int kind, int param, int bits, int32_t *T) {
+    if (!T || bits < 2 || bits > 12 || kind < 0 || kind > 2 || param < 0 || param >= bits) return ORC_BAD_ARG;
+    const int n = 1 << bits, h = n >> 1;
+    for (int a = -h; a < h; ++a)
+        for (int w = -h; w < h; ++w) T[(size_t)(a + h) * n + (size_t)(w + h)] = orc_mul_func(kind, param, a, w);
+    return ORC_OK;
+}
+
+/* acc[m][n] = sum_k T[A[m][k]][W[n][k]], int16 operands, 2 <= bits <= 12 */
+int orc_approx_linear_i16(const int32_t *T, int bits, const int16_t *A, const int16_t *W, int32_t *acc,
+                          long M, long K, long N, int threads) {
+    if (!T || !A || !W || !acc || bits < 2 || bits > 12 || M < 0 || K < 0 || N < 0) return ORC_BAD_ARG;
+    if (!in_range16(A, (size_t)M * K, bits) || !in_range16(W, (size_t)N * K, bits)) return ORC_BAD_ARG;
+    if (threads < 1) threads = 1;
+#pragma omp parallel for num_threads(threads) schedule(static)
+    for (long m = 0; m < M; ++m)
+        for (long n = 0; n < N; ++n) {
+            uint32_t s = 0;
+            for (long k = 0; k < K; ++k) s += lut_at(T, bits, A[m * K + k], W[n * K + k]);
+            acc[m * N + n] = (int32_t)s;
+        }
+    return ORC_OK;
+}
+
+/* acc[m][n] = sum_k f(A[m][k], W[n][k]) with the multiplier evaluated as a function, 2 <= bits <= 16 */
+int orc_approx_linear_func_i16(int kind, int param, int bits, const int16_t *A, const int16_t *W, int32_t *acc,
+                               long M, long K, long N, int threads) {
+    if (!A || !W || !acc || bits < 2 || bits > 16 || kind < 0 || kind > 2 || param < 0 || param >= bits || M < 0 ||
+        K < 0 || N < 0)
+        return ORC_BAD_ARG;
+    if (!in_range16(A, (size_t)M * K, bits) || !in_range16(W, (size_t)N * K, bits)) return ORC_BAD_ARG;
+    if (threads < 1) threads = 1;
+#pragma omp parallel for num_threads(threads) schedule(static)
+    for (long m = 0; m < M; ++m)
+        for (long n = 0; n < N; ++n) {
+            uint32_t s = 0;
+            for (long k = 0; k < K; ++k) s += (uint32_t)orc_mul_func(kind, param, A[m * K + k], W[n * K + k]);
+            acc[m * N + n] = (int32_t)s;
+        }
+    return ORC_OK;
+}
+
+/* 2-D convolution (Sec. III-B, groups = 1), int16 operands: T != NULL takes every product from the table
+ * (bits <= 12), T == NULL evaluates the function (kind, param).  Padded taps meet activation 0 as above. */
+int orc_approx_conv2d_i16(const int32_t *T, int kind, int param, int bits, const int16_t *x, const int16_t *w,
+                          int32_t *acc, long N, long Cin, long H, long W, long Cout, long kh, long kw, long sh,
+                          long sw, long ph, long pw, long dh, long dw, int threads) {
+    if (!x || !w || !acc || bits < 2 || bits > (T ? 12 : 16)) return ORC_BAD_ARG;
+    if (!T && (kind < 0 || kind > 2 || param < 0 || param >= bits)) return ORC_BAD_ARG;
+    if (N < 0 || Cin < 1 || H < 1 || W < 1 || Cout < 1 || kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0 ||
+        dh < 1 || dw < 1)
+        return ORC_BAD_ARG;
+    const long Ho = out_dim(H, kh, sh, ph, dh), Wo = out_dim(W, kw, sw, pw, dw);
+    if (Ho < 1 || Wo < 1) return ORC_BAD_ARG;
+    if (!in_range16(x, (size_t)N * Cin * H * W, bits) || !in_range16(w, (size_t)Cout * Cin * kh * kw, bits))
+        return ORC_BAD_ARG;
+    if (threads < 1) threads = 1;
+#pragma omp parallel for num_threads(threads) schedule(static)
+    for (long n = 0; n < N; ++n)
+        for (long co = 0; co < Cout; ++co)
+            for (long oy = 0; oy < Ho; ++oy)
+                for (long ox = 0; ox < Wo; ++ox) {
+                    uint32_t s = 0;
+                    for (long c = 0; c < Cin; ++c)
+                        for (long ky = 0; ky < kh; ++ky)
+                            for (long kx = 0; kx < kw; ++kx) {
+                                const long iy = oy * sh - ph + ky * dh, ix = ox * sw - pw + kx * dw;
+                                int a = 0;
+                                if (iy >= 0 && iy < H && ix >= 0 && ix < W) a = x[((n * Cin + c) * H + iy) * W + ix];
+                                const int wv = w[((co * Cin + c) * kh + ky) * kw + kx];
+                                s += T ? lut_at(T, bits, a, wv) : (uint32_t)orc_mul_func(kind, param, a, wv);
+                            }
+                    acc[((n * Cout + co) * Ho + oy) * Wo + ox] = (int32_t)s;
+                }
+    return ORC_OK;
+}
+
+/* The quantiser of Sec. III-A for operands of up to 16 bits: q = clamp(rint(x / scale), -Q, Q), Q = 2^(b-1) - 1 */
+int orc_quantize_i16_f32(const float *x, int16_t *q, size_t n, float scale, int bits) {
+    if (!x || !q || bits < 2 || bits > 16 || !(scale > 0.0f)) return ORC_BAD_ARG;
+    const float Q = (float)((1 << (bits - 1)) - 1);
+    for (size_t i = 0; i < n; ++i) {
+        float r = rintf(x[i] / scale);
+        if (r != r) r = 0.0f;
+        if (r > Q) r = Q;
+        if (r < -Q) r = -Q;
+        q[i] = (int16_t)r;
+    }
+    return ORC_OK;
+}
+

@@ -585,3 +585,98 @@ def test_percentile_closed_forms_and_bracketing():
     s = orc.scale_from_amax(c, 8)
     q = orc.quantize(v, s, 8)
     assert np.abs(q).max() == 127 and 0 < np.count_nonzero(np.abs(q) == 127) <= 0.002 * v.size + 2
+
+
+# ---------------------------------------------------------------- operands wider than 8 bits, multipliers as functions
+
+def _rand_i16(rng, shape, bits):
+    h = 1 << (bits - 1)
+    return rng.integers(-h, h, size=shape).astype(np.int16)
+
+
+def test_function_multipliers_closed_forms_and_textbook_values():
+    """Mitchell's multiplier: the textbook values (3x3 -> 8, 5x6 -> 28, 7x7 -> 48), exact on powers of two, never above the
+    true product and at most 11.2 % below it, sign-symmetric, zero for a zero operand.  Truncating multiplier = floor-shifted
+    operands multiplied exactly.  Exact kind = product."""
+    M = orc.FUNC_MITCHELL
+    assert orc.mul_func(M, 0, 3, 3) == 8 and orc.mul_func(M, 0, 5, 6) == 28 and orc.mul_func(M, 0, 7, 7) == 48
+    assert orc.mul_func(M, 0, -5, 6) == -28 and orc.mul_func(M, 0, -7, -7) == 48 and orc.mul_func(M, 0, 6, 5) == 28
+    assert orc.mul_func(M, 0, 0, 77) == 0 and orc.mul_func(M, 0, -2048, 0) == 0
+    for i in range(12):
+        for j in range(12):
+            assert orc.mul_func(M, 0, 1 << i, 1 << j) == 1 << (i + j)
+            assert orc.mul_func(M, 0, 1 << i, 3 << j) == 3 << (i + j)      # one fraction is zero: exact
+    t = orc.table_from_func(M, 0, 10).astype(np.int64)
+    v = np.arange(-512, 512, dtype=np.int64)
+    exact = v[:, None] * v[None, :]
+    assert (np.abs(t) <= np.abs(exact)).all() and (np.sign(t) == np.sign(exact)).all()
+    nz = exact != 0
+    assert (1 - np.abs(t[nz]) / np.abs(exact[nz])).max() <= 1 / 9 + 1e-12       # the known worst case: fractions 1/2, 1/2
+    assert (t == t.T).all()
+    for tb in (1, 3):
+        tt = orc.table_from_func(orc.FUNC_TRUNC, tb, 9).astype(np.int64)
+        v9 = np.arange(-256, 256, dtype=np.int64)
+        want = ((v9[:, None] >> tb) * (v9[None, :] >> tb)) << (2 * tb)
+        assert (tt == want).all()
+    assert (orc.table_from_func(orc.FUNC_EXACT, 0, 10) == exact).all()
+
+
+@pytest.mark.parametrize("bits", [6, 10, 12])
+def test_wide_operands_exact_table_is_integer_gemm_and_conv(bits):
+    rng = np.random.default_rng(100 + bits)
+    A = _rand_i16(rng, (5, 37), bits)
+    W = _rand_i16(rng, (4, 37), bits)
+    ex = orc.table_from_func(orc.FUNC_EXACT, 0, bits)
+    want = A.astype(np.int64) @ W.astype(np.int64).T
+    assert (orc.approx_linear_i16(ex, bits, A, W) == want).all()
+    assert (orc.approx_linear_func_i16(orc.FUNC_EXACT, 0, bits, A, W) == want).all()
+    x = _rand_i16(rng, (2, 3, 7, 6), bits)
+    w = _rand_i16(rng, (4, 3, 3, 3), bits)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(x.astype(np.float64)), torch.from_numpy(w.astype(np.float64)),
+                                     stride=(2, 1), padding=(1, 2), dilation=(1, 2)).numpy()
+    for kw in (dict(lut=ex), dict(func=(orc.FUNC_EXACT, 0))):
+        got = orc.approx_conv2d_i16(bits, x, w, stride=(2, 1), pad=(1, 2), dil=(1, 2), **kw)
+        assert got.shape == ref.shape and (got.astype(np.float64) == ref).all()
+
+
+def test_wide_operands_agree_with_the_8_bit_path_and_table_equals_function():
+    """(i) int16 entry points on 8-bit data = the (separately pinned) int8 entry points, arbitrary table, padding included;
+    (ii) a multiplier as a function and its generated table give identical sums (the 1-1 property of Sec. III-C);
+    (iii) sums wrap around in 32 bits."""
+    rng = np.random.default_rng(321)
+    lut = wl.make_lut(8)
+    A8 = wl.random_i8(rng, (6, 50), 8)
+    W8 = wl.random_i8(rng, (7, 50), 8)
+    assert (orc.approx_linear_i16(lut, 8, A8.astype(np.int16), W8.astype(np.int16)) == orc.approx_linear(lut, 8, A8, W8)).all()
+    x8 = wl.random_i8(rng, (2, 3, 6, 5), 8)
+    w8 = wl.random_i8(rng, (4, 3, 3, 3), 8)
+    assert (orc.approx_conv2d_i16(8, x8.astype(np.int16), w8.astype(np.int16), lut=lut, pad=(1, 1)) ==
+            orc.approx_conv2d(lut, 8, x8, w8, pad=(1, 1))).all()
+    for kind, param, bits in ((orc.FUNC_MITCHELL, 0, 11), (orc.FUNC_TRUNC, 2, 12), (orc.FUNC_MITCHELL, 0, 7)):
+        t = orc.table_from_func(kind, param, bits)
+        A = _rand_i16(rng, (4, 29), bits)
+        W = _rand_i16(rng, (5, 29), bits)
+        assert (orc.approx_linear_i16(t, bits, A, W) == orc.approx_linear_func_i16(kind, param, bits, A, W)).all()
+        x = _rand_i16(rng, (1, 2, 5, 5), bits)
+        w = _rand_i16(rng, (3, 2, 3, 3), bits)
+        assert (orc.approx_conv2d_i16(bits, x, w, lut=t, pad=(1, 1)) ==
+                orc.approx_conv2d_i16(bits, x, w, func=(kind, param), pad=(1, 1))).all()
+    # a function-only width (no table possible): exact kind at 16 bits against int64, wrapped to 32 bits
+    A = _rand_i16(rng, (3, 40), 16)
+    W = _rand_i16(rng, (2, 40), 16)
+    want = (A.astype(np.int64) @ W.astype(np.int64).T).astype(np.uint64).astype(np.uint32).astype(np.int32)
+    got = orc.approx_linear_func_i16(orc.FUNC_EXACT, 0, 16, A, W)
+    assert (got == want).all()
+
+
+def test_quantize_i16_closed_forms():
+    x = np.array([0.0, 0.5, 1.5, 2.5, -0.5, -1.5, 1e9, -1e9, np.nan, 2047.4, -2047.6], dtype=np.float32)
+    q = orc.quantize_i16(x, 1.0, 12)
+    assert q.tolist() == [0, 0, 2, 2, 0, -2, 2047, -2047, 0, 2047, -2047]
+    rng = np.random.default_rng(9)
+    v = rng.standard_normal(1000).astype(np.float32)
+    s = np.float32(0.0123)
+    assert (orc.quantize_i16(v, s, 8) == orc.quantize(v, s, 8)).all()          # same quantiser as the 8-bit one
+    want = np.clip(np.rint(v / s), -32767, 32767).astype(np.int16)
+    assert (orc.quantize_i16(v, s, 16) == want).all()
+
