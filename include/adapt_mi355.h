@@ -265,6 +265,45 @@ int adapt_lstm_step_f32(const adapt_weights *w_hh, const int8_t *qh_dev, const i
                         float s_h, const float *bias_dev, float *c_dev, float *h_dev, int8_t *qh_next_dev, int B, int Hs,
                         void *stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * Operands wider than 8 bits and multipliers given as functions (Sec. III-C "Framework operation": a
+ * table per multiplier or, for large bitwidths, the multiplier described as a function - both a 1-1
+ * representation of the unit; Sec. V evaluates a 12-bit unit).  Operands are int16 in [-H, H-1],
+ * H = 2^(bits-1); same index convention, same sums (int32 wrap-around), padded convolution taps meet
+ * activation 0.  Out-of-range operands are reduced modulo 2^bits in the table form.
+ * ---------------------------------------------------------------------------------------------- */
+
+typedef struct adapt_lut16 adapt_lut16;
+
+/* Device copy of a host table T[(a + H) * 2^bits + (w + H)] of int32 entries, 2 <= bits <= 12 (bits = 12:
+ * 64 MiB, kept in device memory; the kernels gather from it).  Synchronous.  The handle owns its memory. */
+int adapt_lut16_create(adapt_lut16 **out, int bits, const int32_t *table_host);
+/* The table of a function-described multiplier, generated on the device (the table generator of Sec. III-C).
+ * kind 0: exact product.  kind 1: both operands lose their `param` low bits (arithmetic shift), exact multiply,
+ * product shifted back by 2 param.  kind 2: Mitchell's logarithmic multiplier on the magnitudes, sign restored
+ * (param ignored but must be 0 <= param < bits). */
+int adapt_lut16_create_from_func(adapt_lut16 **out, int kind, int param, int bits);
+int adapt_lut16_destroy(adapt_lut16 *lut);
+int adapt_lut16_bits(const adapt_lut16 *lut);
+
+/* q = clamp(rint(x / scale), -Q, Q), Q = 2^(bits-1) - 1, 2 <= bits <= 16: the quantiser of Sec. III-A into int16 */
+int adapt_quantize_i16_f32(const float *x_dev, int16_t *q_dev, size_t n, float scale, int bits, void *stream);
+
+/* acc[m][n] = sum_k T[a[m][k]][w[n][k]]; a_dev [M][K], w_dev [N][K] int16, acc_dev [M][N] int32 */
+int adapt_approx_linear_i16(const adapt_lut16 *lut, const int16_t *a_dev, const int16_t *w_dev, int32_t *acc_dev,
+                            int M, int K, int N, void *stream);
+/* 2-D convolution as adapt_approx_conv2d with groups = 1; x [N][Cin][H][W], w [Cout][Cin][kh][kw] int16 */
+int adapt_approx_conv2d_i16(const adapt_lut16 *lut, const int16_t *x_dev, const int16_t *w_dev, int32_t *acc_dev,
+                            int N, int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w,
+                            int pad_h, int pad_w, int dil_h, int dil_w, void *stream);
+/* The same two layers with the multiplier (kind, param as above) evaluated as a function instead of read from a
+ * table: no table memory, operands of 2 <= bits <= 16.  Identical results to the table form of the same multiplier. */
+int adapt_approx_linear_func_i16(int kind, int param, int bits, const int16_t *a_dev, const int16_t *w_dev,
+                                 int32_t *acc_dev, int M, int K, int N, void *stream);
+int adapt_approx_conv2d_func_i16(int kind, int param, int bits, const int16_t *x_dev, const int16_t *w_dev,
+                                 int32_t *acc_dev, int N, int Cin, int H, int W, int Cout, int kh, int kw,
+                                 int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

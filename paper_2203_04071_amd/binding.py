@@ -32,6 +32,8 @@ EXPORTS = [
     "adapt_linear_layer_f32", "adapt_conv2d_layer_f32", "adapt_conv_transpose2d_layer_f32",
     "adapt_relu_f32", "adapt_add_f32", "adapt_avgpool_hw_f32", "adapt_shortcut_a_f32",
     "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32", "adapt_lstm_cell_q_f32", "adapt_lstm_step_f32", "adapt_gru_cell_f32", "adapt_rnn_cell_f32",
+    "adapt_lut16_create", "adapt_lut16_create_from_func", "adapt_lut16_destroy", "adapt_lut16_bits", "adapt_quantize_i16_f32",
+    "adapt_approx_linear_i16", "adapt_approx_conv2d_i16", "adapt_approx_linear_func_i16", "adapt_approx_conv2d_func_i16",
 ]
 
 
@@ -68,6 +70,15 @@ def load() -> ctypes.CDLL:
     L.adapt_histogram_abs_f32.argtypes = [vp, sz, f32, i32, vp, vp]
     L.adapt_percentile_from_histogram.argtypes = [vp, i32, f32, ctypes.c_uint, ctypes.c_uint, vp, vp]
     L.adapt_quantize_f32.argtypes = [vp, vp, sz, f32, i32, vp]
+    L.adapt_lut16_create.argtypes = [ctypes.POINTER(vp), i32, vp]
+    L.adapt_lut16_create_from_func.argtypes = [ctypes.POINTER(vp), i32, i32, i32]
+    L.adapt_lut16_destroy.argtypes = [vp]
+    L.adapt_lut16_bits.argtypes = [vp]
+    L.adapt_quantize_i16_f32.argtypes = [vp, vp, sz, f32, i32, vp]
+    L.adapt_approx_linear_i16.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
+    L.adapt_approx_conv2d_i16.argtypes = [vp, vp, vp, vp] + [i32] * 13 + [vp]
+    L.adapt_approx_linear_func_i16.argtypes = [i32, i32, i32, vp, vp, vp, i32, i32, i32, vp]
+    L.adapt_approx_conv2d_func_i16.argtypes = [i32, i32, i32, vp, vp, vp] + [i32] * 13 + [vp]
     L.adapt_dequant_i32.argtypes = [vp, vp, sz, sz, sz, f32, vp, vp]
     L.adapt_approx_linear.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
     L.adapt_approx_conv2d.argtypes = [vp, vp, vp, vp] + [i32] * 14 + [vp]
@@ -398,6 +409,98 @@ def adapt_rnn_cell_f32(acc_ih, acc_hh, s_ih: float, s_hh: float, bias, h, relu: 
                                    _ptr(bias, torch.float32), 1 if relu else 0, _ptr(h, torch.float32), _ptr(qh, torch.int8),
                                    float(s_h), bits, B, Hs, _stream(stream)))
     return h, qh
+
+
+# ---- operands wider than 8 bits, multipliers as functions (Sec. III-C)
+
+FUNC_EXACT, FUNC_TRUNC, FUNC_MITCHELL = 0, 1, 2
+
+
+class Lut16:
+    """Owner of an adapt_lut16 handle: a 2^bits x 2^bits int32 table in device memory (bits <= 12), from a host table or
+    generated on the device from a function-described multiplier (func = (kind, param))."""
+
+    def __init__(self, bits: int, table=None, func=None):
+        assert (table is None) != (func is None)
+        self.bits = bits
+        self._h = ctypes.c_void_p()
+        if table is not None:
+            t = np.ascontiguousarray(np.asarray(table, dtype=np.int32))
+            if t.size != (1 << bits) ** 2:
+                raise ValueError("table must have 2^bits x 2^bits entries")
+            _chk(load().adapt_lut16_create(ctypes.byref(self._h), bits, t.ctypes.data_as(ctypes.c_void_p)))
+        else:
+            _chk(load().adapt_lut16_create_from_func(ctypes.byref(self._h), func[0], func[1], bits))
+
+    @property
+    def handle(self):
+        return self._h
+
+    def close(self):
+        if self._h:
+            load().adapt_lut16_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def adapt_quantize_i16_f32(x, scale: float, bits: int, out=None, stream=None):
+    if out is None:
+        out = torch.empty(x.shape, dtype=torch.int16, device=x.device)
+    _chk(load().adapt_quantize_i16_f32(_ptr(x, torch.float32), _ptr(out, torch.int16), x.numel(), float(scale), bits,
+                                       _stream(stream)))
+    return out
+
+
+def adapt_approx_linear_i16(lut: Lut16, a, w, out=None, stream=None):
+    M, K = a.shape
+    N, K2 = w.shape
+    assert K == K2
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=a.device)
+    _chk(load().adapt_approx_linear_i16(lut.handle, _ptr(a, torch.int16), _ptr(w, torch.int16), _ptr(out, torch.int32), M, K, N,
+                                        _stream(stream)))
+    return out
+
+
+def adapt_approx_linear_func_i16(kind: int, param: int, bits: int, a, w, out=None, stream=None):
+    M, K = a.shape
+    N, K2 = w.shape
+    assert K == K2
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=a.device)
+    _chk(load().adapt_approx_linear_func_i16(kind, param, bits, _ptr(a, torch.int16), _ptr(w, torch.int16),
+                                             _ptr(out, torch.int32), M, K, N, _stream(stream)))
+    return out
+
+
+def _conv_i16_out(x, w, stride, pad, dil, out):
+    N, Cin, H, W = x.shape
+    Cout, Cin2, kh, kw = w.shape
+    assert Cin == Cin2
+    if out is None:
+        Ho, Wo = conv_out_hw(H, W, kh, kw, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1])
+        out = torch.empty((N, Cout, Ho, Wo), dtype=torch.int32, device=x.device)
+    return out, (N, Cin, H, W, Cout, kh, kw, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1])
+
+
+def adapt_approx_conv2d_i16(lut: Lut16, x, w, stride=(1, 1), pad=(0, 0), dil=(1, 1), out=None, stream=None):
+    out, dims = _conv_i16_out(x, w, stride, pad, dil, out)
+    _chk(load().adapt_approx_conv2d_i16(lut.handle, _ptr(x, torch.int16), _ptr(w, torch.int16), _ptr(out, torch.int32), *dims,
+                                        _stream(stream)))
+    return out
+
+
+def adapt_approx_conv2d_func_i16(kind: int, param: int, bits: int, x, w, stride=(1, 1), pad=(0, 0), dil=(1, 1), out=None,
+                                 stream=None):
+    out, dims = _conv_i16_out(x, w, stride, pad, dil, out)
+    _chk(load().adapt_approx_conv2d_func_i16(kind, param, bits, _ptr(x, torch.int16), _ptr(w, torch.int16),
+                                             _ptr(out, torch.int32), *dims, _stream(stream)))
+    return out
 
 
 ACT_NONE, ACT_RELU, ACT_TANH = 0, 1, 2

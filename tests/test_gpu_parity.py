@@ -967,3 +967,102 @@ def test_conv_layer_with_per_channel_weights_and_percentile_activations(B):
     yt = B.adapt_conv_transpose2d_layer_f32(B.adapt_weights_pack_conv_transpose2d(B.Lut(lut, bits), dev(wt), 2), xd, s_x, dev(s_out), 1,
                                             bias=dev(bias), act=B.ACT_TANH)
     assert bits_equal(host(yt), orc.tanh(orc.dequant_per_channel(acct, s_out, 4, 24, 24 * 24, bias)))
+
+
+# ------------------------------------------------------------------ operands wider than 8 bits, multipliers as functions
+
+def _rand_i16(rng, shape, bits, dist="gauss"):
+    h = 1 << (bits - 1)
+    if dist == "uniform":
+        return rng.integers(-h, h, size=shape).astype(np.int16)
+    return np.clip(np.rint(rng.standard_normal(shape) * (h / 5.2)), -h, h - 1).astype(np.int16)
+
+
+def test_quantize_i16_bit_exact(B):
+    rng = np.random.default_rng(50)
+    x = np.concatenate([rng.standard_normal(100003) * 3, [0.0, -0.0, 0.5, 1.5, 2.5, -2.5, 1e30, -1e30, np.nan, np.inf]]).astype(np.float32)
+    for bits, s in ((12, 0.0031), (16, 1e-4), (8, 0.05), (2, 1.0)):
+        got = host(B.adapt_quantize_i16_f32(dev(x), s, bits))
+        assert (got == orc.quantize_i16(x, s, bits)).all()
+
+
+BIG_LINEAR = [(1, 1, 1), (64, 256, 128), (300, 77, 19), (1025, 40, 8), (5, 0, 3)]
+
+
+@pytest.mark.parametrize("bits", [9, 12])
+@pytest.mark.parametrize("shape", BIG_LINEAR)
+def test_linear_i16_table_bit_exact(B, bits, shape):
+    M, K, N = shape
+    rng = np.random.default_rng(bits + sum(shape))
+    lut = wl.make_lut(bits)
+    L = B.Lut16(bits, table=lut)
+    for dist in ("gauss", "uniform"):
+        a = _rand_i16(rng, (M, K), bits, dist)
+        w = _rand_i16(rng, (N, K), bits, dist)
+        got = host(B.adapt_approx_linear_i16(L, dev(a), dev(w)))
+        assert (got == orc.approx_linear_i16(lut, bits, a, w, threads=4)).all()
+
+
+BIG_CONV = [
+    # N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw
+    (2, 3, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, 1),
+    (1, 5, 9, 7, 11, 3, 3, 2, 2, 1, 1, 1, 1),
+    (3, 16, 20, 20, 16, 3, 3, 1, 1, 1, 1, 1, 1),
+    (1, 4, 8, 8, 8, 3, 3, 1, 1, 2, 2, 2, 2),
+    (2, 6, 6, 10, 3, 1, 1, 1, 1, 0, 0, 1, 1),
+]
+
+
+@pytest.mark.parametrize("bits", [10, 12])
+@pytest.mark.parametrize("case", BIG_CONV)
+def test_conv2d_i16_table_bit_exact(B, bits, case):
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw = case
+    rng = np.random.default_rng(bits + sum(case))
+    lut = wl.make_lut(bits)
+    x = _rand_i16(rng, (N, Cin, H, W), bits)
+    w = _rand_i16(rng, (Cout, Cin, kh, kw), bits)
+    got = host(B.adapt_approx_conv2d_i16(B.Lut16(bits, table=lut), dev(x), dev(w), (sh, sw), (ph, pw), (dh, dw)))
+    want = orc.approx_conv2d_i16(bits, x, w, lut=lut, stride=(sh, sw), pad=(ph, pw), dil=(dh, dw), threads=4)
+    assert got.shape == want.shape and (got == want).all()
+
+
+@pytest.mark.parametrize("kind,param,bits", [(0, 0, 16), (1, 3, 12), (2, 0, 12), (2, 0, 16), (1, 1, 8), (2, 0, 5)])
+def test_function_multipliers_bit_exact(B, kind, param, bits):
+    rng = np.random.default_rng(kind * 100 + bits)
+    a = _rand_i16(rng, (130, 96), bits, "uniform")
+    w = _rand_i16(rng, (21, 96), bits, "uniform")
+    got = host(B.adapt_approx_linear_func_i16(kind, param, bits, dev(a), dev(w)))
+    assert (got == orc.approx_linear_func_i16(kind, param, bits, a, w, threads=4)).all()
+    x = _rand_i16(rng, (2, 5, 9, 8), bits)
+    f = _rand_i16(rng, (7, 5, 3, 3), bits)
+    got = host(B.adapt_approx_conv2d_func_i16(kind, param, bits, dev(x), dev(f), (1, 1), (1, 1)))
+    assert (got == orc.approx_conv2d_i16(bits, x, f, func=(kind, param), pad=(1, 1), threads=4)).all()
+    if bits <= 12:
+        # the table generated on the device from the function gives the same sums (and equals the oracle's table)
+        L = B.Lut16(bits, func=(kind, param))
+        assert (host(B.adapt_approx_linear_i16(L, dev(a), dev(w))) ==
+                orc.approx_linear_i16(orc.table_from_func(kind, param, bits), bits, a, w, threads=4)).all()
+
+
+def test_wide_table_agrees_with_8_bit_path(B):
+    """The same 8-bit table through the LDS kernels (int8 operands) and through the device-memory gather (int16)."""
+    rng = np.random.default_rng(8)
+    lut = wl.make_lut(8)
+    a = wl.random_i8(rng, (200, 64), 8, "gauss")
+    w = wl.random_i8(rng, (24, 64), 8, "gauss")
+    g8 = host(B.adapt_approx_linear(B.Lut(lut, 8), dev(a), dev(w)))
+    g16 = host(B.adapt_approx_linear_i16(B.Lut16(8, table=lut), dev(a.astype(np.int16)), dev(w.astype(np.int16))))
+    assert (g8 == g16).all()
+
+
+def test_wide_entry_points_refuse_bad_arguments(B):
+    with pytest.raises(B.AdaptError) as e:
+        B.Lut16(13, func=(0, 0))
+    assert e.value.code == -1
+    with pytest.raises(B.AdaptError) as e:
+        B.adapt_approx_linear_func_i16(3, 0, 8, torch.zeros((1, 1), dtype=torch.int16, device="cuda"),
+                                       torch.zeros((1, 1), dtype=torch.int16, device="cuda"))
+    assert e.value.code == -1
+    with pytest.raises(B.AdaptError):
+        B.adapt_quantize_i16_f32(torch.zeros(4, device="cuda"), 0.0, 12)
+
