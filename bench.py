@@ -24,6 +24,8 @@ sys.path.insert(0, ROOT)
 
 LDS_LANES_PER_CLK_PER_CU = 32      # 32 banks x 4 B: one 16-bit gather lane per bank per clock
 MODEL_CLOCK_GHZ = 2.4
+GATHER_LANES_PER_CLK_PER_CU = 4    # vector memory path: one 64-lane gather instruction per 16 clocks
+MITCHELL_OPS_PER_MAC = 15          # vector instructions per multiply-accumulate counted in the compiled function-form kernel (484 per 32)
 MODEL_CUS = 256
 
 # HBM bytes per launch of the dominant call, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, each
@@ -125,6 +127,32 @@ def build_step(cfg_id, bits, torch, B, gnet, wl, eager=False):
         net.forward(x)
         step = _graph_step(gnet, net, x, eager)
         return step, None, 100 * 64 * 3 * 512 * (512 + 512), "extra: GRU 512/512, seq 100, batch 64, 7-bit table", net
+    if cfg_id in (8, 9):    # the layer of configuration 2 with 12-bit operands: table in device memory (8) / Mitchell function (9)
+        c = wl.config2()
+        x = dev(c["x"])
+        w = dev(c["w"])
+        s_x = gnet.calibrated_scale(x, 12)
+        s_w = gnet.calibrated_scale(w, 12)
+        qw = B.adapt_quantize_i16_f32(w, s_w, 12)
+        qx = torch.empty(x.shape, dtype=torch.int16, device="cuda")
+        acc = torch.empty((32, 64, 32, 32), dtype=torch.int32, device="cuda")
+        y = torch.empty((32, 64, 32, 32), dtype=torch.float32, device="cuda")
+        s_out = _f(s_x) * _f(s_w)
+        L = B.Lut16(12, table=wl.make_lut(12)) if cfg_id == 8 else None
+
+        def core():
+            if cfg_id == 8:
+                B.adapt_approx_conv2d_i16(L, qx, qw, (1, 1), (1, 1), out=acc)
+            else:
+                B.adapt_approx_conv2d_func_i16(B.FUNC_MITCHELL, 0, 12, qx, qw, (1, 1), (1, 1), out=acc)
+
+        def step():
+            B.adapt_quantize_i16_f32(x, s_x, 12, out=qx)
+            core()
+            B.adapt_dequant_i32(acc, s_out, 32, 64, 1024, out=y)
+        name = ("extra: approx_conv2d 3x3 s1 p1, batch 32, 64->64 ch, 32x32, 12-bit " +
+                ("table in device memory" if cfg_id == 8 else "Mitchell multiplier as a function"))
+        return step, core, wl.lut_macs_conv2d(32, 64, 32, 32, 64, 3, 3, 1, 1, 1, 1), name, L
     raise SystemExit(f"unknown config {cfg_id}")
 
 
@@ -184,6 +212,19 @@ def cpu_baseline(cfg_id, bits, wl):
         onet.gru(c, threads=th, steps=10)
         dt = time.perf_counter() - t0
         return dict(value=64 * 3 * 512 * 1024 * 10 / dt, unit="LUT-MAC/s", cores=th, kind="oracle", sample="first 10 of 100 time steps")
+    if cfg_id in (8, 9):
+        c = wl.config2()
+        s_x = orc.scale_from_amax(orc.absmax(c["x"]), 12)
+        s_w = orc.scale_from_amax(orc.absmax(c["w"]), 12)
+        qw = orc.quantize_i16(c["w"], s_w, 12)
+        lut = wl.make_lut(12) if cfg_id == 8 else None
+        t0 = time.perf_counter()
+        qx = orc.quantize_i16(c["x"][:8], s_x, 12)
+        acc = orc.approx_conv2d_i16(12, qx, qw, lut=lut, func=None if cfg_id == 8 else (orc.FUNC_MITCHELL, 0), pad=(1, 1), threads=th)
+        orc.dequant(acc, _f(s_x) * _f(s_w), 8, 64, 1024)
+        dt = time.perf_counter() - t0
+        return dict(value=wl.lut_macs_conv2d(8, 64, 32, 32, 64, 3, 3, 1, 1, 1, 1) / dt, unit="LUT-MAC/s", cores=th, kind="oracle",
+                    sample="8 of 32 images, one pass")
     c = wl.config5(bits=bits, batch=32)
     t0 = time.perf_counter()
     onet.dcgan(c, threads=th)
@@ -197,7 +238,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="1-5: the baseline configurations (default 2, the one the metric is quoted on); "
-                    "6: separable convolution block, 7: GRU layer (rows beyond the baseline, not bench lines of record)")
+                    "6: separable convolution block, 7: GRU layer, 8 / 9: the layer of 2 with 12-bit operands, table / function form "
+                    "(rows beyond the baseline, not bench lines of record)")
     ap.add_argument("--bits", type=int, default=8, help="table bits for config 5 (6 or 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="network configurations: launch kernel by kernel instead of replaying a HIP graph")
@@ -260,6 +302,18 @@ def main():
                     traffic=traffic, kernel_ms_avg=k_avg, kernel_ms_min=float(kms.min()),
                     peak_model=f"{cus} CUs x {LDS_LANES_PER_CLK_PER_CU} LDS bank-lanes/clk x {MODEL_CLOCK_GHZ} GHz; "
                                "1 lookup (2 B) per LUT-MAC")
+        if args.config == 8:
+            # a table beyond LDS is gathered through the vector memory path: 4 lane addresses per clock per compute unit
+            gpeak = cus * GATHER_LANES_PER_CLK_PER_CU * MODEL_CLOCK_GHZ * 1e9
+            roof.update(bound="l1-gather", peak=gpeak / 1e12, frac=achieved / gpeak,
+                        peak_model=f"{cus} CUs x {GATHER_LANES_PER_CLK_PER_CU} gathered lanes/clk x {MODEL_CLOCK_GHZ} GHz; "
+                                   "1 lookup (4 B from device memory) per LUT-MAC")
+        if args.config == 9:
+            # the multiplier as a function: vector integer operations, 64 lanes per clock per compute unit
+            apeak = cus * 64 * MODEL_CLOCK_GHZ * 1e9 / MITCHELL_OPS_PER_MAC
+            roof.update(bound="alu", peak=apeak / 1e12, unit="TMAC/s", frac=achieved / apeak,
+                        peak_model=f"{cus} CUs x 64 lanes/clk x {MODEL_CLOCK_GHZ} GHz / {MITCHELL_OPS_PER_MAC} vector "
+                                   "instructions per Mitchell multiply-accumulate")
     else:
         achieved = macs / (ms_per_step * 1e-3)
         roof = dict(bound="lds", achieved=achieved / 1e12, peak=peak / 1e12, unit="Tlookup/s", frac=achieved / peak,
@@ -271,7 +325,8 @@ def main():
         "unit": "LUT-MAC/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8 operands, int16 table, int32 accumulate, fp32 scale",
+        "dtype": ("int8 operands, int16 table, int32 accumulate, fp32 scale" if args.config < 8 else
+                  "int16 operands (12-bit), int32 table or function, int32 accumulate, fp32 scale"),
         "data": "synthetic (seeded)",
         "config": {"workload": name, "lut_macs_per_step": macs},
         "roofline": roof,

@@ -1710,8 +1710,11 @@ namespace {
 int run_big(const adapt_lut16 *lut, int kind, int param, const int16_t *x, const int16_t *w, int32_t *out, adapt::BigParams p, hipStream_t s) {
     if (p.M == 0 || p.N == 0) return ADAPT_OK;
     const long long K = (long long)p.taps * p.Cin;
-    p.Npad = (p.N + adapt::BIG_NT - 1) / adapt::BIG_NT * adapt::BIG_NT;
+    const int NT = lut ? adapt::BIG_NT_TABLE : adapt::BIG_NT_FUNC, threads = lut ? adapt::BIG_THREADS_TABLE : adapt::BIG_THREADS_FUNC;
+    p.Npad = (p.N + NT - 1) / NT * NT;
     if (K * p.Npad > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "weights with more than 2^31-1 packed words");
+    const long long wgs = (long long)((p.M + threads - 1) / threads) * (p.Npad / NT);
+    if (wgs > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "too many workgroups");
     int32_t *words = nullptr;
     HIP_TRY(hipMallocAsync((void **)&words, (size_t)(K > 0 ? K : 1) * p.Npad * sizeof(int32_t), s));
     int rc = ADAPT_OK;
@@ -1723,17 +1726,18 @@ int run_big(const adapt_lut16 *lut, int kind, int param, const int16_t *x, const
         if (pe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "big_pack_weights launch: %s", hipGetErrorString(pe));
     }
     p.x = x; p.words = words; p.out = out;
-    const dim3 grid((unsigned)((p.M + adapt::BIG_THREADS - 1) / adapt::BIG_THREADS), (unsigned)(p.Npad / adapt::BIG_NT));
+    const dim3 grid((unsigned)wgs);
     if (rc == ADAPT_OK) {
+        constexpr int FN = adapt::BIG_NT_FUNC, FT = adapt::BIG_THREADS_FUNC;
         if (lut) {
             adapt::MulTable mt{lut->t_dev, 1 << (lut->bits - 1), (1 << lut->bits) - 1};
-            adapt::big_rows_kernel<<<grid, adapt::BIG_THREADS, 0, s>>>(p, mt);
+            adapt::big_rows_kernel<adapt::MulTable, adapt::BIG_NT_TABLE, adapt::BIG_THREADS_TABLE, true><<<grid, threads, 0, s>>>(p, mt);
         } else if (kind == adapt::FUNC_EXACT) {
-            adapt::big_rows_kernel<<<grid, adapt::BIG_THREADS, 0, s>>>(p, adapt::MulFunc<adapt::FUNC_EXACT>{param});
+            adapt::big_rows_kernel<adapt::MulFunc<adapt::FUNC_EXACT>, FN, FT, false><<<grid, threads, 0, s>>>(p, adapt::MulFunc<adapt::FUNC_EXACT>{param});
         } else if (kind == adapt::FUNC_TRUNC) {
-            adapt::big_rows_kernel<<<grid, adapt::BIG_THREADS, 0, s>>>(p, adapt::MulFunc<adapt::FUNC_TRUNC>{param});
+            adapt::big_rows_kernel<adapt::MulFunc<adapt::FUNC_TRUNC>, FN, FT, false><<<grid, threads, 0, s>>>(p, adapt::MulFunc<adapt::FUNC_TRUNC>{param});
         } else {
-            adapt::big_rows_kernel<<<grid, adapt::BIG_THREADS, 0, s>>>(p, adapt::MulFunc<adapt::FUNC_MITCHELL>{param});
+            adapt::big_rows_kernel<adapt::MulFunc<adapt::FUNC_MITCHELL>, FN, FT, false><<<grid, threads, 0, s>>>(p, adapt::MulFunc<adapt::FUNC_MITCHELL>{param});
         }
         hipError_t le = hipGetLastError();
         if (le != hipSuccess) rc = fail(ADAPT_ERR_HIP, "big_rows launch: %s", hipGetErrorString(le));

@@ -8,18 +8,23 @@
 // distribution reaches), which the vector L1 and the L2 serve.  The function form evaluates the multiplier in the
 // vector ALU and needs no memory at all; it covers operands of up to 16 bits.
 //
-// One kernel serves both: lanes along the GEMM rows (output pixels), NT output channels per lane; per inner index the
-// lane loads one activation and the NT weight words arrive through scalar loads (pre-packed [K][Npad] int32: element
-// offset of the weight's table row, or the weight itself for the function form).  No LDS, 256 lanes per workgroup, so
-// many workgroups per compute unit hide the gather latency.
+// One kernel template serves both: lanes along the GEMM rows (output pixels), NT output channels per lane; per inner index
+// the lane loads one activation and the NT weight words arrive through scalar loads (pre-packed [K][Npad] int32: element
+// offset of the weight's table row, or the weight itself for the function form).  No LDS.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 namespace adapt {
 
-constexpr int BIG_THREADS = 256;
-constexpr int BIG_NT = 8;
+// function form: 256 lanes, 8 channels per lane (the weight-side arithmetic is shared by the wave, the activation-side
+// arithmetic by the 8 channels).  table form: 1024 lanes, 1 channel per lane, the waves of a workgroup kept in step by a
+// barrier every four inner indices - all 16 waves then gather from the same table row at the same time and the vector L1
+// (32 KB) serves most of their lines.  Measured on the 12-bit 3x3 layer (1.2 G lookups): 8 rows per step and free-running
+// waves 3.7 ms with 30 L2 requests per gather instruction and a quarter of them missing L2 (20 GB fetched); the same with
+// channel tiles spread over the XCDs 3.1 ms; 2 rows in step 1.7 ms; 1 row in step 1.6 ms with 7 L2 requests per gather.
+constexpr int BIG_THREADS_FUNC = 256, BIG_NT_FUNC = 8;
+constexpr int BIG_THREADS_TABLE = 1024, BIG_NT_TABLE = 1;
 
 enum { FUNC_EXACT = 0, FUNC_TRUNC = 1, FUNC_MITCHELL = 2 };
 
@@ -29,13 +34,15 @@ enum { FUNC_EXACT = 0, FUNC_TRUNC = 1, FUNC_MITCHELL = 2 };
 __device__ __forceinline__ int32_t mul_func(int kind, int t, int a, int w) {
     if (kind == FUNC_EXACT) return a * w;
     if (kind == FUNC_TRUNC) return (int32_t)((uint32_t)((a >> t) * (w >> t)) << (2 * t));
+    // branch-free: a zero operand runs through the arithmetic with a harmless stand-in and is selected away at the end
     const uint32_t ma = (uint32_t)(a < 0 ? -a : a), mw = (uint32_t)(w < 0 ? -w : w);
-    if (ma == 0 || mw == 0) return 0;
-    const int ka = 31 - __clz((int)ma), kw = 31 - __clz((int)mw);
+    const int ka = 31 - __clz((int)(ma | 1u)), kw = 31 - __clz((int)(mw | 1u));
     const uint32_t s = ((ma - (1u << ka)) << kw) + ((mw - (1u << kw)) << ka);
     const uint32_t one = 1u << (ka + kw);
-    const uint32_t pr = s < one ? one + s : 2u * s;
-    return ((a < 0) != (w < 0)) ? -(int32_t)pr : (int32_t)pr;
+    uint32_t pr = s < one ? one + s : 2u * s;
+    pr = (ma == 0 || mw == 0) ? 0u : pr;
+    const uint32_t m = (uint32_t)((a ^ w) >> 31);       // all ones when the signs differ
+    return (int32_t)((pr ^ m) - m);
 }
 
 struct MulTable {       // weight word = element offset of the table row of the weight
@@ -98,13 +105,16 @@ struct BigParams {
     int kstride, img_stride;
 };
 
-template <class Mul>
-__global__ __launch_bounds__(BIG_THREADS) void big_rows_kernel(const BigParams p, const Mul mul) {
-    constexpr int NT = BIG_NT;
-    const int m = blockIdx.x * BIG_THREADS + threadIdx.x;
+template <class Mul, int NT, int THREADS, bool IN_STEP>
+__global__ __launch_bounds__(THREADS) void big_rows_kernel(const BigParams p, const Mul mul) {
+    // workgroup id -> (channel tile fastest, then row tile): consecutive workgroups go to different XCDs, so each L2
+    // serves the table rows of few channel tiles (with 8 tiles: of one) instead of all of them
+    const int n_tiles = p.Npad / NT;
+    const int n_tile = blockIdx.x % n_tiles, m_tile = blockIdx.x / n_tiles;
+    const int m = m_tile * THREADS + threadIdx.x;
     const bool mvalid = m < p.M;
     const int mm = mvalid ? m : p.M - 1;
-    const int n0 = blockIdx.y * NT;
+    const int n0 = n_tile * NT;
     const int img = mm / p.HoWo, pix = mm - img * p.HoWo;
     const int oy = pix / p.Wo, ox = pix - oy * p.Wo;
     const int16_t *xb = p.x + (size_t)img * p.img_stride;
@@ -133,9 +143,13 @@ __global__ __launch_bounds__(BIG_THREADS) void big_rows_kernel(const BigParams p
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
                 const int32_t *w4 = wr + (size_t)(c + kk) * p.Npad;
+                int32_t ww[NT];                 // the NT words of this inner index: one scalar load
 #pragma unroll
-                for (int n = 0; n < NT; ++n) acc[n] += mul(a[kk], w4[n]);
+                for (int n = 0; n < NT; ++n) ww[n] = w4[n];
+#pragma unroll
+                for (int n = 0; n < NT; ++n) acc[n] += mul(a[kk], ww[n]);
             }
+            if (IN_STEP) __syncthreads();       // (uniform trip counts: every lane of the workgroup gets here)
         }
         for (; c < p.Cin; ++c) {
             const int v = xp[(size_t)c * p.kstride];
