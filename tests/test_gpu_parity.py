@@ -1066,3 +1066,53 @@ def test_wide_entry_points_refuse_bad_arguments(B):
     with pytest.raises(B.AdaptError):
         B.adapt_quantize_i16_f32(torch.zeros(4, device="cuda"), 0.0, 12)
 
+
+# ------------------------------------------------------------------ the workloads beyond the baseline at the sizes bench.py times
+
+def test_separable_block_full_size_as_benchmarked(B):
+    """bench.py --config 6: depthwise 3x3 + pointwise 1x1, batch 32, 128 channels, 32x32; whole tensors."""
+    from oracle import networks as onet
+    from paper_2203_04071_amd import networks as gnet
+    cfg = wl.separable_workload(batch=32, cin=128, cout=128, hw=32)
+    want = onet.separable_conv(cfg, threads=orc.host_threads())
+    net = gnet.SeparableConv(cfg)
+    net.forward(dev(cfg["x"]))                  # calibration
+    got = gnet.Captured(net, dev(cfg["x"])).replay()          # frozen scales, as a graph replay like the benchmark
+    torch.cuda.synchronize()
+    assert (host(got["acc_dw"]) == want["acc_dw"]).all()
+    assert_f32_close(host(got["out"]), want["out"])
+
+
+def test_gru_full_size_as_benchmarked(B):
+    """bench.py --config 7: GRU 512/512, batch 64, 7-bit table; the first 12 of the 100 time steps against the oracle
+    (the recurrence makes every later step depend on all earlier ones, so a defect shows in the first steps)."""
+    from oracle import networks as onet
+    from paper_2203_04071_amd import networks as gnet
+    cfg = wl.recurrent_workload("gru", seq=100, batch=64, isz=512, hsz=512, bits=7)
+    want = onet.gru(cfg, threads=orc.host_threads(), steps=12)
+    got = gnet.Recurrent(cfg, "gru").forward(dev(cfg["x"]))
+    assert got["s_x"] == want["s_x"]
+    assert (host(got["acc_ih"][:12]) == want["acc_ih"]).all()
+    assert bits_equal(host(got["hs"][:12]), want["hs"])
+
+
+@pytest.mark.parametrize("form", ["table", "function"])
+def test_12_bit_layer_full_size_as_benchmarked(B, form):
+    """bench.py --config 8 / 9: the 3x3 layer of configuration 2 with 12-bit operands; whole tensor."""
+    c = wl.config2()
+    th = orc.host_threads()
+    s_x = orc.scale_from_amax(orc.absmax(c["x"]), 12)
+    s_w = orc.scale_from_amax(orc.absmax(c["w"]), 12)
+    oqx, oqw = orc.quantize_i16(c["x"], s_x, 12), orc.quantize_i16(c["w"], s_w, 12)
+    qx = B.adapt_quantize_i16_f32(dev(c["x"]), s_x, 12)
+    qw = B.adapt_quantize_i16_f32(dev(c["w"]), s_w, 12)
+    assert (host(qx) == oqx).all() and (host(qw) == oqw).all()
+    if form == "table":
+        lut = wl.make_lut(12)
+        got = B.adapt_approx_conv2d_i16(B.Lut16(12, table=lut), qx, qw, (1, 1), (1, 1))
+        want = orc.approx_conv2d_i16(12, oqx, oqw, lut=lut, pad=(1, 1), threads=th)
+    else:
+        got = B.adapt_approx_conv2d_func_i16(B.FUNC_MITCHELL, 0, 12, qx, qw, (1, 1), (1, 1))
+        want = orc.approx_conv2d_i16(12, oqx, oqw, func=(orc.FUNC_MITCHELL, 0), pad=(1, 1), threads=th)
+    assert (host(got) == want).all()
+
