@@ -718,6 +718,35 @@ const uint4 *ensure_wide(const adapt_weights *h, hipStream_t s) {
     return d;
 }
 
+adapt::FastDiv fast_div(uint32_t d) {
+    int l = 0;
+    while ((1ull << l) < d) ++l;
+    adapt::FastDiv f;
+    f.k = 31 + l;
+    f.M = (uint32_t)((1ull << f.k) / d + 1);
+    f.d = d;
+    return f;
+}
+
+// zero-padded activation copy of a convolution's input (int8, or fp32 quantised on the way)
+int launch_pad(const LayerIO *io, const int8_t *x, int bits, int8_t *xt, int N, int C, int H, int W, int ph, int pw, int Cp, int xmajor,
+               hipStream_t s) {
+    const size_t total = (size_t)N * (H + 2 * ph) * (W + 2 * pw) * (Cp / 4);
+    size_t blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    if (!blocks) return ADAPT_OK;
+    const adapt::FastDiv dwp = fast_div((uint32_t)(W + 2 * pw)), dc4 = fast_div((uint32_t)(Cp / 4)), dhp = fast_div((uint32_t)(H + 2 * ph));
+    const int fast = total < 0x7fffffffull ? 1 : 0;
+    if (io && io->xf)
+        adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcF32{io->xf, io->s_x, io->Q, (1u << bits) - 1u}, xt, N, C, H, W,
+                                                                         ph, pw, Cp, xmajor, dwp, dc4, dhp, fast);
+    else
+        adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcI8{x, (1u << bits) - 1u}, xt, N, C, H, W, ph, pw, Cp, xmajor,
+                                                                         dwp, dc4, dhp, fast);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
 // activation side of a linear layer: A itself when its rows are a multiple of 32 bytes, else a zero-padded copy
 int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *a, int32_t *out, int M, hipStream_t s,
                  Workspace *ws, const LayerIO *io = nullptr, const adapt_weights *wh = nullptr) {
@@ -791,13 +820,8 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     {
         int wrc = ws_get(ws, copy_bytes + part_bytes, s, (void **)&xt);
         if (wrc) return wrc;
-        const size_t total = xt_bytes / 4;
-        size_t blocks = (total + 255) / 256;
-        if (blocks > 65536) blocks = 65536;
-        if (io && io->xf)
-            adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcF32{io->xf, io->s_x, io->Q, (1u << bits) - 1u}, xt, N, q.Cin, H, W, ph,
-                                                                             pw, Cp, xmajor);
-        else adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcI8{x, (1u << bits) - 1u}, xt, N, q.Cin, H, W, ph, pw, Cp, xmajor);
+        int prc = launch_pad(io, x, bits, xt, N, q.Cin, H, W, ph, pw, Cp, xmajor, s);
+        if (prc) return ws_put(ws, xt, s, prc);
     }
     LinesCall c;
     c.M = M; c.HoWo = Ho * Wo; c.Wo = Wo;
@@ -845,13 +869,8 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
     {
         int wrc = ws_get(ws, copy_bytes + part_bytes, s, (void **)&xt);
         if (wrc) return wrc;
-        const size_t total = xt_bytes / 4;
-        size_t blocks = (total + 255) / 256;
-        if (blocks > 65536) blocks = 65536;
-        if (io && io->xf)
-            adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcF32{io->xf, io->s_x, io->Q, (1u << bits) - 1u}, xt, N, q.Cin, H, W,
-                                                                             Ty - 1, Tx - 1, Cp, xmajor);
-        else adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcI8{x, (1u << bits) - 1u}, xt, N, q.Cin, H, W, Ty - 1, Tx - 1, Cp, xmajor);
+        int prc = launch_pad(io, x, bits, xt, N, q.Cin, H, W, Ty - 1, Tx - 1, Cp, xmajor, s);
+        if (prc) return ws_put(ws, xt, s, prc);
     }
     LinesCall c;
     c.M = M; c.HoWo = Qy * Qx; c.Wo = Qx;

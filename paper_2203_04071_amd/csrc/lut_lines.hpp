@@ -118,20 +118,43 @@ struct SrcF32 {
 //   xmajor == 0: channel-last            [N][H + 2 ph][W + 2 pw][Cp]
 //   xmajor == 1: groups of four channels [N][H + 2 ph][Cp / 4][W + 2 pw][4]  (the four channel bytes of
 //                consecutive pixels are adjacent, so 4 rows x 4 channels of a lane are 16 contiguous bytes)
+// Division of a 31-bit number by a launch-invariant divisor as multiply + shift: q = (n * M) >> k with
+// k = 31 + ceil(log2 d), M = floor(2^k / d) + 1, exact for every n < 2^31 (the error term n / 2^k stays below 1 / d).
+// An integer division costs about 35 vector instructions, and the copy kernels below are bound by instruction count.
+struct FastDiv {
+    uint32_t M;
+    int k;
+    uint32_t d;
+    __device__ __forceinline__ uint32_t div(uint32_t n) const { return (uint32_t)(((uint64_t)n * M) >> k); }
+};
+
 template <typename Src>
 __global__ void pad_channels_last_kernel(const Src x, int8_t *__restrict__ xt, int N, int C, int H,
-                                         int W, int ph, int pw, int Cp, int xmajor) {
+                                         int W, int ph, int pw, int Cp, int xmajor, FastDiv dwp, FastDiv dc4, FastDiv dhp,
+                                         int fast) {
     const int Hp = H + 2 * ph, Wp = W + 2 * pw;
     const size_t total = (size_t)N * Hp * Wp * (Cp / 4);
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
         // consecutive threads walk along x for a fixed group of 4 channels: reads coalesce per channel plane
-        const int xp = (int)(i % Wp);
-        size_t r = i / Wp;
-        const int c4 = (int)(r % (Cp / 4));
-        r /= (Cp / 4);
-        const int yp = (int)(r % Hp);
-        const int n = (int)(r / Hp);
+        int xp, c4, yp, n;
+        if (fast) {             // total < 2^31
+            const uint32_t i32 = (uint32_t)i;
+            const uint32_t r1 = dwp.div(i32);
+            xp = (int)(i32 - r1 * dwp.d);
+            const uint32_t r2 = dc4.div(r1);
+            c4 = (int)(r1 - r2 * dc4.d);
+            const uint32_t r3 = dhp.div(r2);
+            yp = (int)(r2 - r3 * dhp.d);
+            n = (int)r3;
+        } else {
+            xp = (int)(i % Wp);
+            size_t r = i / Wp;
+            c4 = (int)(r % (Cp / 4));
+            r /= (Cp / 4);
+            yp = (int)(r % Hp);
+            n = (int)(r / Hp);
+        }
         const int y = yp - ph, xx = xp - pw;
         uint32_t v = 0;
         if (y >= 0 && y < H && xx >= 0 && xx < W) {
