@@ -509,8 +509,13 @@ int launch_lines_xmajor(const adapt::LinesParams &p, unsigned grid, hipStream_t 
 }
 
 // wide-line kernel: 8 rows per lane from an x-major copy, signed single-pass tables
-int launch_lines_wide(const adapt::LinesParams &p, unsigned grid, hipStream_t s) {
-    if (p.bits == 8) adapt::lut_lines_wide_kernel<4><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+// (extra: the instantiation whose epilogue also takes the border terms of a transposed convolution off and knows tanh)
+int launch_lines_wide(const adapt::LinesParams &p, unsigned grid, bool extra, hipStream_t s) {
+    if (extra) {
+        if (p.bits == 8) adapt::lut_lines_wide_kernel<4, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+        else if (p.bits == 7) adapt::lut_lines_wide_kernel<2, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+        else adapt::lut_lines_wide_kernel<1, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    } else if (p.bits == 8) adapt::lut_lines_wide_kernel<4><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
     else if (p.bits == 7) adapt::lut_lines_wide_kernel<2><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
     else adapt::lut_lines_wide_kernel<1><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
     HIP_TRY(hipGetLastError());
@@ -580,6 +585,10 @@ struct LinesCall {       // per-call geometry of the activation side
     // single-pass tables without tap pairing.
     const uint4 *dt_wide = nullptr;
     int32_t *partial = nullptr;         // room for the partial sums when the plan splits the inner dimension
+    // transposed convolution: zero sums and geometry for taking the border terms off inside the kernel (see
+    // adapt::LinesParams::zsum); run_lines reports through border_done whether it did
+    const int32_t *zsum = nullptr;
+    int cv_Ho = 0, cv_Wo = 0, cv_H = 0, cv_W = 0, cv_kh = 0, cv_kw = 0, cv_s = 1, cv_pad = 0, cv_Ly = 0, cv_Lx = 0;
     size_t out_elems = 0;               // elements of the whole output tensor
     size_t out_channels = 1, out_inner = 1;     // where the channel sits in a flat output index: (i / inner) % channels
 };
@@ -588,6 +597,16 @@ int device_cus() {
     int cu = 256, dev = 0;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
     return cu;
+}
+
+adapt::FastDiv fast_div(uint32_t d) {
+    int l = 0;
+    while ((1ull << l) < d) ++l;
+    adapt::FastDiv f;
+    f.k = 31 + l;
+    f.M = (uint32_t)((1ull << f.k) / d + 1);
+    f.d = d;
+    return f;
 }
 
 // How a product is spread over the chip.  Rows per lane R (a workgroup handles 128 R rows): as many as still give every
@@ -627,7 +646,8 @@ size_t lines_partial_bytes(int M, int tiles, int Cc, int taps, size_t out_elems)
 }
 
 int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *xt, const LinesCall &c,
-              int32_t *out, hipStream_t s, const LayerIO *io = nullptr, bool may_fuse = true) {
+              int32_t *out, hipStream_t s, const LayerIO *io = nullptr, bool may_fuse = true, bool *border_done = nullptr,
+              bool *finished = nullptr) {
     const int n_phases = (int)c.phases.size();
     const LinesPlan pl = lines_plan(c.M, q.n_tiles * n_phases, q.k_cc(), q.k_taps());
     const int R = pl.R;
@@ -645,16 +665,30 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     p.out_plane = c.out_plane; p.out_sy = c.out_sy; p.out_sx = c.out_sx;
     p.m_tiles = (c.M + 128 * R - 1) / (128 * R);
     p.ksplit = pl.ksplit; p.gps = pl.gps; p.ks_out_stride = split ? (long long)c.out_elems : 0;
-    const bool fuse = may_fuse && io && io->fused(storage);
-    const bool fuse_in_kernel = fuse && !split;
-    p.deq = fuse_in_kernel ? 1 : 0; p.act = fuse_in_kernel ? io->act : 0;
-    p.scale = fuse_in_kernel ? io->s_out : 1.0f; p.bias = fuse_in_kernel ? io->bias : nullptr;
-    p.scales = fuse_in_kernel ? io->s_out_vec : nullptr;
-    p.resid = fuse_in_kernel ? io->resid : nullptr;
     // one base offset per lane is enough when the R rows of a lane are equally spaced in xt
     const bool regular = (c.M % R == 0) && (c.HoWo == 1 || c.Wo % R == 0);
     const bool xmajor = c.xmajor && R == 8 && c.M % 8 == 0 && c.Wo % 4 == 0;
     if (c.xmajor && !xmajor) return fail(ADAPT_ERR_HIP, "lines path: x-major copy without 8 rows per lane in runs of 4 pixels");
+    const bool use_wide = xmajor && c.dt_wide && storage == 0 && !q.pair_g;
+    // the wide kernel has an instantiation that takes the border terms of a transposed convolution off itself and
+    // knows tanh; the kernel that adds split sums knows tanh too
+    const bool border_in_kernel = c.zsum && !split && use_wide;
+    if (border_done) *border_done = border_in_kernel;
+    const bool act_ok = io && (io->act <= 1 || (io->act == 2 && (split || use_wide)));
+    const bool fuse = (may_fuse || border_in_kernel) && io && io->deq && storage == 0 && act_ok;
+    if (finished) *finished = fuse;
+    const bool fuse_in_kernel = fuse && !split;
+    const bool extra = use_wide && (border_in_kernel || (fuse_in_kernel && io->act == 2));
+    p.zsum = border_in_kernel ? c.zsum : nullptr;
+    p.cv_plane = fast_div((uint32_t)(border_in_kernel ? c.cv_Ho * c.cv_Wo : 1));
+    p.cv_wo = fast_div((uint32_t)(border_in_kernel ? c.cv_Wo : 1));
+    p.cv_s = fast_div((uint32_t)c.cv_s);
+    p.cv_Ho = c.cv_Ho; p.cv_Wo = c.cv_Wo; p.cv_H = c.cv_H; p.cv_W = c.cv_W; p.cv_kh = c.cv_kh; p.cv_kw = c.cv_kw;
+    p.cv_pad = c.cv_pad; p.cv_Ly = c.cv_Ly; p.cv_Lx = c.cv_Lx;
+    p.deq = fuse_in_kernel ? 1 : 0; p.act = fuse_in_kernel ? io->act : 0;
+    p.scale = fuse_in_kernel ? io->s_out : 1.0f; p.bias = fuse_in_kernel ? io->bias : nullptr;
+    p.scales = fuse_in_kernel ? io->s_out_vec : nullptr;
+    p.resid = fuse_in_kernel ? io->resid : nullptr;
     int rc = ADAPT_OK;
     for (int half = 0; half <= storage && rc == ADAPT_OK; ++half) {
         p.dt = dt[half];
@@ -669,9 +703,9 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
             }
             const long long grid = (long long)p.m_tiles * q.n_tiles * p.phases * p.ksplit;
             if (grid > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "lines path: grid too large");
-            if (xmajor && c.dt_wide && storage == 0 && !q.pair_g) {
+            if (use_wide) {
                 p.dt = c.dt_wide;
-                rc = launch_lines_wide(p, (unsigned)grid, s);
+                rc = launch_lines_wide(p, (unsigned)grid, extra, s);
             } else if (xmajor) rc = sgn ? launch_lines_xmajor<true>(p, (unsigned)grid, s) : launch_lines_xmajor<false>(p, (unsigned)grid, s);
             else if (R == 8) rc = launch_lines_r<8>(p, (unsigned)grid, sgn, regular, s);
             else if (R == 4) rc = launch_lines_r<4>(p, (unsigned)grid, sgn, regular, s);
@@ -716,16 +750,6 @@ const uint4 *ensure_wide(const adapt_weights *h, hipStream_t s) {
     }
     h->dtw_dev = d;
     return d;
-}
-
-adapt::FastDiv fast_div(uint32_t d) {
-    int l = 0;
-    while ((1ull << l) < d) ++l;
-    adapt::FastDiv f;
-    f.k = 31 + l;
-    f.M = (uint32_t)((1ull << f.k) / d + 1);
-    f.d = d;
-    return f;
 }
 
 // zero-padded activation copy of a convolution's input (int8, or fp32 quantised on the way)
@@ -796,9 +820,10 @@ int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
         c.out_plane = 1; c.out_sy = 0; c.out_sx = 0;
     }
     if (part_bytes) c.partial = reinterpret_cast<int32_t *>(tmp + copy_bytes);
-    int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io);
+    bool finished = false;
+    int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io, true, nullptr, &finished);
     rc = ws_put(ws, tmp, s, rc);
-    if (rc == ADAPT_OK && io && io->deq && !io->fused(storage)) rc = finish_inplace(out, (size_t)M * q.N, (size_t)q.N, 1, *io, s);
+    if (rc == ADAPT_OK && io && io->deq && !finished) rc = finish_inplace(out, (size_t)M * q.N, (size_t)q.N, 1, *io, s);
     return rc;
 }
 
@@ -835,9 +860,10 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     c.out_elems = out_elems; c.out_channels = (size_t)q.N; c.out_inner = (size_t)Ho * Wo;
     if (part_bytes) c.partial = reinterpret_cast<int32_t *>(xt + copy_bytes);
     if (xmajor) c.dt_wide = ensure_wide(wh, s);
-    int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io);
+    bool finished = false;
+    int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io, true, nullptr, &finished);
     rc = ws_put(ws, xt, s, rc);
-    if (rc == ADAPT_OK && io && io->deq && !io->fused(storage))
+    if (rc == ADAPT_OK && io && io->deq && !finished)
         rc = finish_inplace(out, (size_t)M * q.N, (size_t)q.N, (size_t)Ho * Wo, *io, s);
     return rc;
 }
@@ -897,10 +923,19 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
     c.out_elems = out_elems; c.out_channels = (size_t)q.N; c.out_inner = (size_t)Ho * Wo;
     if (part_bytes) c.partial = reinterpret_cast<int32_t *>(xt + copy_bytes);
     if (xmajor) c.dt_wide = ensure_wide(wh, s);
-    int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io, !border);
+    if (border && out_elems < 0x7fffffffull) {      // let the product kernel take the border terms off where it can
+        c.zsum = zsum;
+        c.cv_Ho = Ho; c.cv_Wo = Wo; c.cv_H = H; c.cv_W = W; c.cv_kh = kh; c.cv_kw = kw; c.cv_s = st; c.cv_pad = pad; c.cv_Ly = Ly; c.cv_Lx = Lx;
+    }
+    bool border_done = false, finished = false;
+    int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io, !border, &border_done, &finished);
     rc = ws_put(ws, xt, s, rc);
     if (rc != ADAPT_OK) return rc;
     const size_t planes = (size_t)N * q.N;
+    if (border_done) {      // sums corrected in the product kernel's epilogue (and rescaled there, if it could)
+        if (io && io->deq && !finished) return finish_inplace(out, planes * Ho * Wo, (size_t)q.N, (size_t)Ho * Wo, *io, s);
+        return ADAPT_OK;
+    }
     const int nrows = 2 * Ly < Ho ? 2 * Ly : Ho, ncols = 2 * Lx < Wo ? 2 * Lx : Wo;
     const size_t work[2] = {planes * nrows * Wo, planes * (size_t)(Ho - nrows) * ncols};
     for (int region = 0; region < 2; ++region) {
@@ -911,7 +946,7 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
                                                                        Lx, region);
         HIP_TRY(hipGetLastError());
     }
-    if (io && io->deq && (border || !io->fused(storage))) return finish_inplace(out, planes * Ho * Wo, (size_t)q.N, (size_t)Ho * Wo, *io, s);
+    if (io && io->deq && (border || !finished)) return finish_inplace(out, planes * Ho * Wo, (size_t)q.N, (size_t)Ho * Wo, *io, s);
     return ADAPT_OK;
 }
 

@@ -38,6 +38,16 @@ typedef short short2_t __attribute__((ext_vector_type(2)));
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
+// Division of a 31-bit number by a launch-invariant divisor as multiply + shift: q = (n * M) >> k with
+// k = 31 + ceil(log2 d), M = floor(2^k / d) + 1, exact for every n < 2^31 (the error term n / 2^k stays below 1 / d).
+// An integer division costs about 35 vector instructions, and the copy kernels below are bound by instruction count.
+struct FastDiv {
+    uint32_t M;
+    int k;
+    uint32_t d;
+    __device__ __forceinline__ uint32_t div(uint32_t n) const { return (uint32_t)(((uint64_t)n * M) >> k); }
+};
+
 struct LinesParams {
     const int8_t *xt;       // activations (see above)
     const uint4 *dt;        // derived tables [n_tiles][steps][2^b lines][8 columns] x 16 B
@@ -79,16 +89,48 @@ struct LinesParams {
     // 4 * (j % pair_cg) + step of it (pair_cg = Cp / 4).  `taps` then counts groups and Cc is 4; taps_real is the
     // number of filter taps (taps beyond it are padding: all-zero tables).
     int pair_g, pair_cg, taps_real;
+    // Transposed convolution with the border terms taken off in the epilogue (zsum != nullptr; single-pass tables, no
+    // split of the inner dimension): the phase convolutions look up every window tap, also those over the zero border
+    // of the padded copy, but the layer is defined over real (input, weight) pairs only; zsum[co][tap] = sum over the
+    // input channels of T[0][w] is what such a tap added.  Output and input sizes, filter, stride, padding, and the
+    // widths Ly / Lx of the output border in which some tap has no input pixel.
+    const int32_t *zsum;
+    FastDiv cv_plane, cv_wo, cv_s;      // divisions by Ho * Wo, Wo, stride
+    int cv_Ho, cv_Wo, cv_H, cv_W, cv_kh, cv_kw, cv_pad, cv_Ly, cv_Lx;
 };
 
 // what is stored for the finished sum v of output channel n (see LinesParams::deq)
 // off: element offset of the output position (for the residual input)
+// EXTRA: the instantiation also knows the border terms of a transposed convolution (LinesParams::zsum) and tanh; the
+// plain one carries neither (eight inlined copies of that code in an epilogue cost the ordinary layers about a
+// microsecond per launch)
+template <bool EXTRA = false>
 __device__ __forceinline__ uint32_t finish_sum(const LinesParams &p, uint32_t v, int n, size_t off) {
+    if (EXTRA && p.zsum) {       // transposed convolution: output pixel from the offset, border terms off (rare: border pixels only)
+        const uint32_t o = (uint32_t)off;
+        const uint32_t pix = o - p.cv_plane.div(o) * p.cv_plane.d;
+        const int oy = (int)p.cv_wo.div(pix), ox = (int)(pix - (uint32_t)oy * p.cv_wo.d);
+        if (oy < p.cv_Ly || oy >= p.cv_Ho - p.cv_Ly || ox < p.cv_Lx || ox >= p.cv_Wo - p.cv_Lx) {
+            const int st = (int)p.cv_s.d;
+            const int qy = (int)p.cv_s.div((uint32_t)(oy + p.cv_pad)), ry = oy + p.cv_pad - qy * st;
+            const int qx = (int)p.cv_s.div((uint32_t)(ox + p.cv_pad)), rx = ox + p.cv_pad - qx * st;
+            uint32_t extra = 0;
+            for (int m = 0; m * st + ry < p.cv_kh; ++m) {
+                const bool yin = qy - m >= 0 && qy - m < p.cv_H;
+                for (int nn = 0; nn * st + rx < p.cv_kw; ++nn) {
+                    const bool xin = qx - nn >= 0 && qx - nn < p.cv_W;
+                    if (!(yin && xin)) extra += (uint32_t)p.zsum[(size_t)n * p.cv_kh * p.cv_kw + (ry + st * m) * p.cv_kw + (rx + st * nn)];
+                }
+            }
+            v -= extra;
+        }
+    }
     if (!p.deq) return v;
     float y = (float)(int32_t)v * (p.scales ? p.scales[n] : p.scale);
     if (p.bias) y = y + p.bias[n];
     if (p.resid) y = y + p.resid[off];
     if (p.act == 1) y = y > 0.0f ? y : 0.0f;
+    else if (EXTRA && p.act == 2) y = tanh_spec(y);
     return __float_as_uint(y);
 }
 
@@ -118,16 +160,6 @@ struct SrcF32 {
 //   xmajor == 0: channel-last            [N][H + 2 ph][W + 2 pw][Cp]
 //   xmajor == 1: groups of four channels [N][H + 2 ph][Cp / 4][W + 2 pw][4]  (the four channel bytes of
 //                consecutive pixels are adjacent, so 4 rows x 4 channels of a lane are 16 contiguous bytes)
-// Division of a 31-bit number by a launch-invariant divisor as multiply + shift: q = (n * M) >> k with
-// k = 31 + ceil(log2 d), M = floor(2^k / d) + 1, exact for every n < 2^31 (the error term n / 2^k stays below 1 / d).
-// An integer division costs about 35 vector instructions, and the copy kernels below are bound by instruction count.
-struct FastDiv {
-    uint32_t M;
-    int k;
-    uint32_t d;
-    __device__ __forceinline__ uint32_t div(uint32_t n) const { return (uint32_t)(((uint64_t)n * M) >> k); }
-};
-
 template <typename Src>
 __global__ void pad_channels_last_kernel(const Src x, int8_t *__restrict__ xt, int N, int C, int H,
                                          int W, int ph, int pw, int Cp, int xmajor, FastDiv dwp, FastDiv dc4, FastDiv dhp,

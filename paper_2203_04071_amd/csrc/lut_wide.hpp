@@ -114,7 +114,7 @@ __device__ __forceinline__ void wide_fetch(u32x4_t &v, uint32_t word, uint32_t c
 
 // DOPS: table copy operations per wave and step = 2^b * 256 B / (16 waves * 1 KB): 4 / 2 / 1 for b = 8 / 7 / <= 6
 // (smaller tables: one operation with fewer lanes).
-template <int DOPS>
+template <int DOPS, bool EXTRA = false>
 __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const LinesParams p) {
     __shared__ __attribute__((aligned(256))) uint4 tbl[2 * (WIDE_BUF_BYTES / 16)];      // 128 KB
     const int tid = threadIdx.x;
@@ -308,7 +308,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const Lin
         const int sx = p.out_sx;
         uint32_t f[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) f[i] = p.shift < 0 ? finish_sum(p, w[i][t], n, (size_t)(q0 + i * sx - outp)) : w[i][t];
+        for (int i = 0; i < 4; ++i) f[i] = p.shift < 0 ? finish_sum<EXTRA>(p, w[i][t], n, (size_t)(q0 + i * sx - outp)) : w[i][t];
         if (p.shift < 0 && sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
             *reinterpret_cast<uint4 *>(q0) = make_uint4(f[0], f[1], f[2], f[3]);
         } else {
