@@ -680,8 +680,6 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     const bool fuse_in_kernel = fuse && !split;
     const bool extra = use_wide && (border_in_kernel || (fuse_in_kernel && io->act == 2));
     p.zsum = border_in_kernel ? c.zsum : nullptr;
-    p.cv_plane = fast_div((uint32_t)(border_in_kernel ? c.cv_Ho * c.cv_Wo : 1));
-    p.cv_wo = fast_div((uint32_t)(border_in_kernel ? c.cv_Wo : 1));
     p.cv_s = fast_div((uint32_t)c.cv_s);
     p.cv_Ho = c.cv_Ho; p.cv_Wo = c.cv_Wo; p.cv_H = c.cv_H; p.cv_W = c.cv_W; p.cv_kh = c.cv_kh; p.cv_kw = c.cv_kw;
     p.cv_pad = c.cv_pad; p.cv_Ly = c.cv_Ly; p.cv_Lx = c.cv_Lx;

@@ -95,36 +95,33 @@ struct LinesParams {
     // input channels of T[0][w] is what such a tap added.  Output and input sizes, filter, stride, padding, and the
     // widths Ly / Lx of the output border in which some tap has no input pixel.
     const int32_t *zsum;
-    FastDiv cv_plane, cv_wo, cv_s;      // divisions by Ho * Wo, Wo, stride
+    FastDiv cv_s;                       // division by the stride
     int cv_Ho, cv_Wo, cv_H, cv_W, cv_kh, cv_kw, cv_pad, cv_Ly, cv_Lx;
 };
 
 // what is stored for the finished sum v of output channel n (see LinesParams::deq)
 // off: element offset of the output position (for the residual input)
-// EXTRA: the instantiation also knows the border terms of a transposed convolution (LinesParams::zsum) and tanh; the
-// plain one carries neither (eight inlined copies of that code in an epilogue cost the ordinary layers about a
-// microsecond per launch)
-template <bool EXTRA = false>
-__device__ __forceinline__ uint32_t finish_sum(const LinesParams &p, uint32_t v, int n, size_t off) {
-    if (EXTRA && p.zsum) {       // transposed convolution: output pixel from the offset, border terms off (rare: border pixels only)
-        const uint32_t o = (uint32_t)off;
-        const uint32_t pix = o - p.cv_plane.div(o) * p.cv_plane.d;
-        const int oy = (int)p.cv_wo.div(pix), ox = (int)(pix - (uint32_t)oy * p.cv_wo.d);
-        if (oy < p.cv_Ly || oy >= p.cv_Ho - p.cv_Ly || ox < p.cv_Lx || ox >= p.cv_Wo - p.cv_Lx) {
-            const int st = (int)p.cv_s.d;
-            const int qy = (int)p.cv_s.div((uint32_t)(oy + p.cv_pad)), ry = oy + p.cv_pad - qy * st;
-            const int qx = (int)p.cv_s.div((uint32_t)(ox + p.cv_pad)), rx = ox + p.cv_pad - qx * st;
-            uint32_t extra = 0;
-            for (int m = 0; m * st + ry < p.cv_kh; ++m) {
-                const bool yin = qy - m >= 0 && qy - m < p.cv_H;
-                for (int nn = 0; nn * st + rx < p.cv_kw; ++nn) {
-                    const bool xin = qx - nn >= 0 && qx - nn < p.cv_W;
-                    if (!(yin && xin)) extra += (uint32_t)p.zsum[(size_t)n * p.cv_kh * p.cv_kw + (ry + st * m) * p.cv_kw + (rx + st * nn)];
-                }
-            }
-            v -= extra;
+// What the window taps WITHOUT an input pixel added to output pixel (oy, ox) of channel co of a transposed convolution
+// (see LinesParams::zsum); zero away from the border.
+__device__ __forceinline__ uint32_t convt_border_terms(const LinesParams &p, int co, int oy, int ox) {
+    const int st = (int)p.cv_s.d;
+    const int qy = (int)p.cv_s.div((uint32_t)(oy + p.cv_pad)), ry = oy + p.cv_pad - qy * st;
+    const int qx = (int)p.cv_s.div((uint32_t)(ox + p.cv_pad)), rx = ox + p.cv_pad - qx * st;
+    uint32_t extra = 0;
+    for (int m = 0; m * st + ry < p.cv_kh; ++m) {
+        const bool yin = qy - m >= 0 && qy - m < p.cv_H;
+        for (int nn = 0; nn * st + rx < p.cv_kw; ++nn) {
+            const bool xin = qx - nn >= 0 && qx - nn < p.cv_W;
+            if (!(yin && xin)) extra += (uint32_t)p.zsum[(size_t)co * p.cv_kh * p.cv_kw + (ry + st * m) * p.cv_kw + (rx + st * nn)];
         }
     }
+    return extra;
+}
+
+// EXTRA: the instantiation also knows tanh; the plain one does not (eight inlined copies of that code in an epilogue
+// cost the ordinary layers about a microsecond per launch)
+template <bool EXTRA = false>
+__device__ __forceinline__ uint32_t finish_sum(const LinesParams &p, uint32_t v, int n, size_t off) {
     if (!p.deq) return v;
     float y = (float)(int32_t)v * (p.scales ? p.scales[n] : p.scale);
     if (p.bias) y = y + p.bias[n];

@@ -300,10 +300,24 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const Lin
     reduce_scatter<8>(acc, j, w);
     int img, a0, b0;
     row_pos(r0 + 4 * hq, img, a0, b0);
+    // transposed convolution (EXTRA instantiation, zsum given): the phase's output pixels of this run of 4 are
+    // (oy, ox + i * out_sx); the taps that lay over the zero border are taken off for the few runs that touch the border
+    int oy = 0, ox = 0;
+    bool near_border = false;
+    if (EXTRA && p.zsum) {
+        const int oy0 = out_off / p.cv_Wo, ox0 = out_off - oy0 * p.cv_Wo;       // uniform: once per workgroup
+        oy = oy0 + a0 * (p.out_sy / p.cv_Wo);
+        ox = ox0 + b0 * p.out_sx;
+        near_border = oy < p.cv_Ly || oy >= p.cv_Ho - p.cv_Ly || ox < p.cv_Lx || ox + 3 * p.out_sx >= p.cv_Wo - p.cv_Lx;
+    }
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
         const int n = nt * 8 + 4 * t + cq;
         if (n >= p.N) continue;
+        if (EXTRA && near_border) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) w[i][t] -= convt_border_terms(p, n, oy, ox + i * p.out_sx);
+        }
         int32_t *q0 = outp + ((size_t)img * p.N + n) * p.out_plane + out_off + a0 * p.out_sy + b0 * p.out_sx;
         const int sx = p.out_sx;
         uint32_t f[4];
