@@ -249,8 +249,8 @@ def main():
                     help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc (reported as roofline.traffic)")
     args = ap.parse_args()
     if args.gpus != 1:
-        raise SystemExit("bench.py: this build runs on one GPU only (pure batch sharding needs no exchange step; "
-                         "see DESIGN.md). Run with --gpus 1.")
+        raise SystemExit("bench.py: this build runs on one GPU only (pure batch sharding would need no exchange step). "
+                         "Run with --gpus 1.")
 
     import torch
     from paper_2203_04071_amd import binding as B, networks as gnet, workloads as wl

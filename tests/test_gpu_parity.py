@@ -1116,3 +1116,34 @@ def test_12_bit_layer_full_size_as_benchmarked(B, form):
         want = orc.approx_conv2d_i16(12, oqx, oqw, func=(orc.FUNC_MITCHELL, 0), pad=(1, 1), threads=th)
     assert (host(got) == want).all()
 
+
+def test_stored_small_cases(B):
+    """The HIP path on the inputs of tests/golden/oracle_small_cases.json (expected values written by the oracle)."""
+    import json
+    import os
+    with open(os.path.join(os.path.dirname(__file__), "golden", "oracle_small_cases.json")) as f:
+        g = json.load(f)
+    L = B.Lut(wl.make_lut(4), 4)
+    i8 = lambda v: dev(np.array(v, dtype=np.int8))
+    c = g["linear_4bit"]
+    assert host(B.adapt_approx_linear(L, i8(c["A"]), i8(c["W"]))).tolist() == c["acc"]
+    c = g["conv2d_4bit_pad1"]
+    assert host(B.adapt_approx_conv2d(L, i8(c["x"]), i8(c["w"]), (1, 1), (1, 1))).tolist() == c["acc"]
+    c = g["conv_transpose2d_4bit_s2_p1"]
+    assert host(B.adapt_approx_conv_transpose2d(L, i8(c["x"]), i8(c["w"]), 2, 1)).tolist() == c["acc"]
+    c = g["quantize_8bit"]
+    assert host(B.adapt_quantize_f32(dev(np.array(c["x"], dtype=np.float32)), c["scale"], 8)).tolist() == c["q"]
+    c = g["lstm_cell"]
+    cd = dev(np.array(c["c"], dtype=np.float32))
+    hd = torch.empty((2, 2), dtype=torch.float32, device="cuda")
+    B.adapt_lstm_cell_f32(dev(np.array(c["acc_ih"], dtype=np.int32)), dev(np.array(c["acc_hh"], dtype=np.int32)), 1e-3, 2e-3, None, cd, hd)
+    assert host(hd).view(np.uint32).tolist() == c["h_bits"] and host(cd).view(np.uint32).tolist() == c["c_bits"]
+    c = g["gru_cell"]
+    hd = torch.empty((2, 2), dtype=torch.float32, device="cuda")
+    B.adapt_gru_cell_f32(dev(np.array(c["acc_ih"], dtype=np.int32)), dev(np.array(c["acc_hh"], dtype=np.int32)), 1e-3, 2e-3, None, None,
+                         dev(np.array(c["h"], dtype=np.float32)), hd)
+    assert host(hd).view(np.uint32).tolist() == c["h_bits"]
+    a = dev(np.full((64, 1), 21, dtype=np.int16))
+    w = dev(np.arange(-32, 32, dtype=np.int16).reshape(64, 1))
+    assert host(B.adapt_approx_linear_func_i16(B.FUNC_MITCHELL, 0, 6, a, w))[0].tolist() == g["mitchell_6bit_row_of_21"]
+

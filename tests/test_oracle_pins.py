@@ -680,3 +680,19 @@ def test_quantize_i16_closed_forms():
     want = np.clip(np.rint(v / s), -32767, 32767).astype(np.int16)
     assert (orc.quantize_i16(v, s, 16) == want).all()
 
+
+def test_oracle_reproduces_its_stored_small_cases():
+    """tests/golden/oracle_small_cases.json was written by tests/golden/make_golden.py from the oracle alone; a change of
+    the oracle's arithmetic shows up here (and has to be justified from the paper when the file is regenerated)."""
+    import json
+    import os
+    import importlib.util
+    here = os.path.join(os.path.dirname(__file__), "golden")
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    with open(os.path.join(here, "oracle_small_cases.json")) as f:
+        stored = json.load(f)
+    now = json.loads(json.dumps(mod.cases()))
+    assert now == stored
+
