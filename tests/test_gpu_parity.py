@@ -1147,3 +1147,122 @@ def test_stored_small_cases(B):
     w = dev(np.arange(-32, 32, dtype=np.int16).reshape(64, 1))
     assert host(B.adapt_approx_linear_func_i16(B.FUNC_MITCHELL, 0, 6, a, w))[0].tolist() == g["mitchell_6bit_row_of_21"]
 
+# ------------------------------------------------------------------ random shapes through every entry point
+
+@pytest.mark.parametrize("seed", [11, 12])
+def test_random_shapes_match_oracle(B, seed):
+    """Seeded random shapes (ragged sizes, strides, dilations, groups, table widths incl. a two-pass table, fused layer
+    calls with bias / residual / activations, transposed convolutions, function multipliers) against the oracle: exercises
+    the choice between kernels at sizes nobody picked by hand."""
+    ncases = 120
+    rng = np.random.default_rng(seed)
+    luts = {b: wl.make_lut(b) for b in (4, 6, 7, 8)}
+    big = (rng.integers(-2**20, 2**20, size=(64, 64))).astype(np.int32)   # two-pass table at 6 bits
+    L = {b: B.Lut(luts[b], b) for b in luts}
+    Lbig = B.Lut(big, 6)
+    bad = []
+    for it in range(ncases):
+        kind = rng.choice(["linear", "conv", "convg", "convt", "layer", "convt_layer", "lin_layer", "i16"])
+        bits = int(rng.choice([4, 6, 7, 8]))
+        two = bits == 6 and rng.random() < 0.3
+        lut, LL = (big, Lbig) if two else (luts[bits], L[bits])
+        desc = None
+        try:
+            if kind == "linear" or kind == "lin_layer":
+                M = int(rng.choice([1, 3, 64, 130, 4096, 4100, 5000])); K = int(rng.integers(1, 200)); N = int(rng.integers(1, 70))
+                a = wl.random_i8(rng, (M, K), bits, "gauss"); w = wl.random_i8(rng, (N, K), bits, "gauss")
+                desc = (kind, bits, two, M, K, N)
+                want = orc.approx_linear(lut, bits, a, w, threads=8)
+                if kind == "linear":
+                    got = host(B.adapt_approx_linear(LL, dev(a), dev(w)))
+                    ok = (got == want).all()
+                    pw = B.adapt_weights_pack_linear(LL, dev(w))
+                    ok = ok and (host(B.adapt_approx_linear_packed(pw, dev(a))) == want).all()
+                else:
+                    x = (rng.standard_normal((M, K))).astype(np.float32)
+                    s_x = orc.scale_from_amax(orc.absmax(x), bits)
+                    qa = orc.quantize(x, s_x, bits)
+                    want = orc.approx_linear(lut, bits, qa, w, threads=8)
+                    bias = rng.standard_normal(N).astype(np.float32)
+                    y = orc.dequant(want, np.float32(s_x) * np.float32(0.01), M, N, 1, bias)
+                    y = np.maximum(y, 0)
+                    pw = B.adapt_weights_pack_linear(LL, dev(w))
+                    got = host(B.adapt_linear_layer_f32(pw, dev(x), s_x, np.float32(s_x) * np.float32(0.01), bias=dev(bias), act=B.ACT_RELU))
+                    ok = np.array_equal(got.view(np.uint32), y.view(np.uint32))
+            elif kind in ("conv", "convg", "layer"):
+                g = 1
+                if kind == "convg":
+                    g = int(rng.choice([2, 3, 4, 8]))
+                cg = int(rng.integers(1, 20)); og = int(rng.integers(1, 20))
+                if kind == "convg" and rng.random() < 0.4:
+                    cg, og = 1, int(rng.choice([1, 1, 2]))
+                    g = int(rng.integers(2, 40))
+                Cin, Cout = cg * g, og * g
+                if kind != "convg" and rng.random() < 0.5:
+                    Cin = int(rng.choice([8, 16, 32, 64, 96])); Cout = int(rng.choice([8, 16, 24, 64])); cg, og = Cin, Cout
+                N = int(rng.choice([1, 2, 5, 16])); H = int(rng.integers(3, 40)); W = int(rng.integers(3, 40))
+                kh = int(rng.choice([1, 3, 5])); kw = int(rng.choice([1, 3, 5]))
+                sh = int(rng.choice([1, 1, 2])); sw = int(rng.choice([1, 1, 2])); ph = int(rng.integers(0, 3)); pw_ = int(rng.integers(0, 3))
+                dh = int(rng.choice([1, 1, 2])); dw = int(rng.choice([1, 1, 2]))
+                if H + 2 * ph < dh * (kh - 1) + 1 or W + 2 * pw_ < dw * (kw - 1) + 1:
+                    continue
+                x = wl.random_i8(rng, (N, Cin, H, W), bits, "gauss"); w = wl.random_i8(rng, (Cout, cg, kh, kw), bits, "gauss")
+                desc = (kind, bits, two, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw_, dh, dw, g)
+                want = orc.approx_conv2d(lut, bits, x, w, (sh, sw), (ph, pw_), (dh, dw), g, threads=8)
+                if kind != "layer":
+                    got = host(B.adapt_approx_conv2d(LL, dev(x), dev(w), (sh, sw), (ph, pw_), (dh, dw), groups=g))
+                    ok = (got == want).all()
+                    if g == 1:
+                        pk = B.adapt_weights_pack_conv2d(LL, dev(w))
+                        ok = ok and (host(B.adapt_approx_conv2d_packed(pk, dev(x), (sh, sw), (ph, pw_), (dh, dw))) == want).all()
+                else:
+                    xf = rng.standard_normal((N, Cin, H, W)).astype(np.float32)
+                    s_x = orc.scale_from_amax(orc.absmax(xf), bits)
+                    qx = orc.quantize(xf, s_x, bits)
+                    want = orc.approx_conv2d(lut, bits, qx, w, (sh, sw), (ph, pw_), (dh, dw), 1, threads=8)
+                    n_, c_, h_, w_ = want.shape
+                    bias = rng.standard_normal(Cout).astype(np.float32)
+                    res = rng.standard_normal(want.shape).astype(np.float32)
+                    s_o = np.float32(s_x) * np.float32(0.02)
+                    y = orc.dequant(want, s_o, n_, c_, h_ * w_, bias)
+                    y = np.maximum(orc.add(y, res), 0)
+                    pk = B.adapt_weights_pack_conv2d(LL, dev(w))
+                    got = host(B.adapt_conv2d_layer_f32(pk, dev(xf), s_x, s_o, (sh, sw), (ph, pw_), (dh, dw), bias=dev(bias), act=B.ACT_RELU, residual=dev(res)))
+                    ok = np.array_equal(got.view(np.uint32), y.view(np.uint32))
+            elif kind in ("convt", "convt_layer"):
+                N = int(rng.choice([1, 2, 9, 40])); Cin = int(rng.integers(1, 40)); Cout = int(rng.integers(1, 30))
+                H = int(rng.integers(1, 12)); W = int(rng.integers(1, 12)); k = int(rng.choice([2, 3, 4, 5])); s = int(rng.choice([1, 2, 3])); p = int(rng.integers(0, 3))
+                if (H - 1) * s - 2 * p + k < 1 or (W - 1) * s - 2 * p + k < 1:
+                    continue
+                x = wl.random_i8(rng, (N, Cin, H, W), bits, "gauss"); w = wl.random_i8(rng, (Cin, Cout, k, k), bits, "gauss")
+                desc = (kind, bits, two, N, Cin, H, W, Cout, k, s, p)
+                want = orc.approx_conv_transpose2d(lut, bits, x, w, s, p, threads=8)
+                pk = B.adapt_weights_pack_conv_transpose2d(LL, dev(w), s)
+                if kind == "convt":
+                    ok = (host(B.adapt_approx_conv_transpose2d(LL, dev(x), dev(w), s, p)) == want).all()
+                    ok = ok and (host(B.adapt_approx_conv_transpose2d_packed(pk, dev(x), p)) == want).all()
+                else:
+                    xf = rng.standard_normal((N, Cin, H, W)).astype(np.float32)
+                    s_x = orc.scale_from_amax(orc.absmax(xf), bits)
+                    want = orc.approx_conv_transpose2d(lut, bits, orc.quantize(xf, s_x, bits), w, s, p, threads=8)
+                    n_, c_, h_, w_ = want.shape
+                    s_o = np.float32(s_x) * np.float32(0.02)
+                    act = int(rng.choice([0, 1, 2]))
+                    y = orc.dequant(want, s_o, n_, c_, h_ * w_)
+                    y = np.maximum(y, 0) if act == 1 else (orc.tanh(y) if act == 2 else y)
+                    got = host(B.adapt_conv_transpose2d_layer_f32(pk, dev(xf), s_x, s_o, p, act=act))
+                    ok = np.array_equal(got.view(np.uint32), y.view(np.uint32))
+            else:
+                b16 = int(rng.choice([9, 10, 12])); M = int(rng.choice([1, 70, 1030])); K = int(rng.integers(1, 60)); N = int(rng.integers(1, 20))
+                h = 1 << (b16 - 1)
+                a = rng.integers(-h, h, (M, K)).astype(np.int16); w = rng.integers(-h, h, (N, K)).astype(np.int16)
+                kindf = int(rng.choice([0, 1, 2])); par = int(rng.integers(0, 4)) if kindf == 1 else 0
+                desc = (kind, b16, M, K, N, kindf, par)
+                ok = (host(B.adapt_approx_linear_func_i16(kindf, par, b16, dev(a), dev(w))) == orc.approx_linear_func_i16(kindf, par, b16, a, w, threads=8)).all()
+        except B.AdaptError as e:
+            bad.append((desc, str(e)))
+            continue
+        if not ok:
+            bad.append(desc)
+    assert not bad, bad
+
