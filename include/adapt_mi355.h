@@ -179,6 +179,25 @@ int adapt_approx_conv2d_packed(const adapt_weights *w, const int8_t *x_dev, int3
 int adapt_approx_conv_transpose2d_packed(const adapt_weights *w, const int8_t *x_dev, int32_t *acc_dev, int N, int H, int W,
                                          int pad, void *stream);
 
+/* Chained convolution layers (Sec. III-A / IV: quantise -> table-lookup layer -> dequantise per layer; here the
+ * re-quantisation for the NEXT layer happens in this layer's epilogue).  adapt_conv2d_chain_prepare fixes the place
+ * and layout of `h`'s quantised, zero-padded input copy for one input geometry and zeroes it (borders and padded
+ * channels stay zero afterwards); it may re-allocate the handle's workspace, so call it before recording a graph.
+ * adapt_conv2d_layer_chain_f32 is adapt_conv2d_layer_f32 with two additions:
+ *   x_dev == NULL: the input copy is already in the prepared workspace of `h` (written by the layer before);
+ *   next != NULL : y is ALSO written into the prepared workspace of `next` as its input copy, quantised with
+ *                  s_next exactly as adapt_quantize_f32 would quantise y_dev (the output y_dev is still written).
+ * `next` must have been prepared for N images of this layer's output size and have as many input channels as this
+ * layer has output channels; otherwise ADAPT_ERR_INVALID_ARGUMENT.  An ordinary call on a prepared handle with
+ * another geometry ends its prepared state.  Results are identical to the unchained calls. */
+int adapt_conv2d_chain_prepare(const adapt_weights *w, int N, int H, int W, int stride_h, int stride_w, int pad_h,
+                               int pad_w, int dil_h, int dil_w, void *stream);
+int adapt_conv2d_layer_chain_f32(const adapt_weights *w, const float *x_dev, float *y_dev, int N, int H, int W,
+                                 int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, float s_x,
+                                 float s_out, const float *s_out_vec_dev, const float *bias_dev,
+                                 const float *residual_dev, int act, const adapt_weights *next, float s_next,
+                                 void *stream);
+
 /* ------------------------------------------------------------------------------------------------
  * Whole layers on packed weights with fp32 activations on both sides (Sec. III-A/III-B: a layer quantises its input,
  * multiplies through the table and rescales the sums):

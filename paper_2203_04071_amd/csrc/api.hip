@@ -86,12 +86,15 @@ struct LayerIO {
     const float *s_out_vec = nullptr;   // one output scale per channel instead of s_out
     const float *bias = nullptr;
     const float *resid = nullptr;       // fp32 tensor of the output's shape, added after the bias and before act
+    adapt::ChainOut chain{};            // also write the output as the next convolution's quantised input copy (buf != nullptr)
+    int chain_wo = 1;                   // width of the output (for the kernels that walk it element by element)
     // rescaling inside the product kernel needs a single table pass and an activation it knows
     bool fused(int storage) const { return deq && storage == 0 && act <= 1; }
 };
 
 int finish_inplace(int32_t *buf, size_t n, size_t channels, size_t inner, const LayerIO &io, hipStream_t s) {
-    adapt::finish_inplace_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, s>>>(buf, n, channels, inner, io.s_out, io.s_out_vec, io.bias, io.resid, io.act);
+    adapt::finish_inplace_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, s>>>(buf, n, channels, inner, io.s_out, io.s_out_vec, io.bias, io.resid, io.act,
+                                                                          io.chain, io.chain_wo);
     HIP_TRY(hipGetLastError());
     return ADAPT_OK;
 }
@@ -130,6 +133,12 @@ struct adapt_weights {
     int8_t *w8_dev;         // copy of the weights for the geometries the phase form does not cover
     const adapt_lut *lut;   // the table handle (must outlive this handle), for those geometries
     mutable Workspace ws;   // padded activation copy of the latest call
+    // convolutions: the geometry for which the workspace was prepared to receive its input copy from the layer before
+    // (adapt_conv2d_chain_prepare): borders and padded channels zeroed, layout fixed
+    mutable struct ChainIn {
+        bool valid = false;
+        int N = 0, H = 0, W = 0, sh = 0, sw = 0, ph = 0, pw = 0, dh = 0, dw = 0, xmajor = 0;
+    } chain_in;
     // linear layers only: row offsets [K][wofs_npad] for the whole-table kernel, which serves short activation matrices
     // transposed convolutions: the same for the gather form (wofs_dev, [kh kw Cin][wofs_npad]) and for the single-pixel
     // form, a linear layer with Cout kh kw outputs (wofs1_dev, [Cin][wofs1_npad])
@@ -678,7 +687,9 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     const bool fuse = (may_fuse || border_in_kernel) && io && io->deq && storage == 0 && act_ok;
     if (finished) *finished = fuse;
     const bool fuse_in_kernel = fuse && !split;
-    const bool extra = use_wide && (border_in_kernel || (fuse_in_kernel && io->act == 2));
+    const bool chain_in_kernel = fuse_in_kernel && io->chain.buf;
+    const bool extra = use_wide && (border_in_kernel || (fuse_in_kernel && io->act == 2) || chain_in_kernel);
+    p.chain = chain_in_kernel ? io->chain : adapt::ChainOut{};
     p.zsum = border_in_kernel ? c.zsum : nullptr;
     p.cv_s = fast_div((uint32_t)c.cv_s);
     p.cv_Ho = c.cv_Ho; p.cv_Wo = c.cv_Wo; p.cv_H = c.cv_H; p.cv_W = c.cv_W; p.cv_kh = c.cv_kh; p.cv_kw = c.cv_kw;
@@ -713,7 +724,7 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
             adapt::reduce_partials_kernel<<<ew_grid(c.out_elems), adapt::EW_THREADS, 0, s>>>(
                 c.partial, pl.ksplit, c.out_elems, out, c.out_elems, half == 0 ? -1 : 16, (fuse && half == 0) ? 1 : 0, c.out_channels,
                 c.out_inner, fuse ? io->s_out : 1.0f, fuse ? io->s_out_vec : nullptr, fuse ? io->bias : nullptr, fuse ? io->resid : nullptr,
-                fuse ? io->act : 0);
+                fuse ? io->act : 0, (fuse && half == 0) ? io->chain : adapt::ChainOut{}, io ? io->chain_wo : 1);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) rc = fail(ADAPT_ERR_HIP, "reduce_partials launch: %s", hipGetErrorString(e));
         }
@@ -828,7 +839,7 @@ int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
 // activation side of a convolution: zero-padded channel-last copy of x
 int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *x, int32_t *out, int N, int H,
                  int W, int Ho, int Wo, int sh, int sw, int ph, int pw, int dh, int dw, hipStream_t s, Workspace *ws,
-                 const LayerIO *io = nullptr, const adapt_weights *wh = nullptr) {
+                 const LayerIO *io = nullptr, const adapt_weights *wh = nullptr, bool input_ready = false) {
     const int Hp = H + 2 * ph, Wp = W + 2 * pw, Cp = q.Cp;
     const size_t xt_bytes = (size_t)N * Hp * Wp * Cp;
     // With 8 rows per lane that are 8 consecutive output pixels of a stride-1 convolution, the copy is laid
@@ -841,10 +852,21 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     const size_t copy_bytes = ((xt_bytes + 64 + 255) / 256) * 256;
     int8_t *xt = nullptr;
     {
-        int wrc = ws_get(ws, copy_bytes + part_bytes, s, (void **)&xt);
-        if (wrc) return wrc;
-        int prc = launch_pad(io, x, bits, xt, N, q.Cin, H, W, ph, pw, Cp, xmajor, s);
-        if (prc) return ws_put(ws, xt, s, prc);
+        if (input_ready) {      // the layer before wrote the copy (adapt_conv2d_chain_prepare fixed its place and layout)
+            if (!ws || !ws->ptr || ws->bytes < copy_bytes + part_bytes || !wh || wh->chain_in.xmajor != xmajor)
+                return fail(ADAPT_ERR_INVALID_ARGUMENT, "chained convolution: the input buffer was not prepared for this geometry");
+            xt = static_cast<int8_t *>(ws->ptr);
+        } else {
+            if (wh && wh->chain_in.valid) {     // an ordinary call with another geometry ends the prepared state
+                const auto &ci = wh->chain_in;
+                if (ci.N != N || ci.H != H || ci.W != W || ci.sh != sh || ci.sw != sw || ci.ph != ph || ci.pw != pw || ci.dh != dh || ci.dw != dw)
+                    wh->chain_in.valid = false;
+            }
+            int wrc = ws_get(ws, copy_bytes + part_bytes, s, (void **)&xt);
+            if (wrc) return wrc;
+            int prc = launch_pad(io, x, bits, xt, N, q.Cin, H, W, ph, pw, Cp, xmajor, s);
+            if (prc) return ws_put(ws, xt, s, prc);
+        }
     }
     LinesCall c;
     c.M = M; c.HoWo = Ho * Wo; c.Wo = Wo;
@@ -1464,28 +1486,106 @@ int adapt_linear_layer_f32(const adapt_weights *h, const float *x_dev, float *y_
     return lines_linear(h->bits, h->storage, shape_of(h), h->dt_dev, nullptr, out, M, s, &h->ws, &io, h);
 }
 
+// geometry shared by the convolution layer calls
+struct ConvGeo {
+    long long Ho, Wo;
+};
+
+static int conv_geo(const adapt_weights *h, int N, int H, int W, int sh, int sw, int ph, int pw, int dh, int dw, ConvGeo *g, const char *who) {
+    if (N < 0 || H < 1 || W < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0 || dh < 1 || dw < 1)
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
+    const long long eh = (long long)H + 2LL * ph - (long long)dh * (h->kh - 1) - 1;
+    const long long ew = (long long)W + 2LL * pw - (long long)dw * (h->kw - 1) - 1;
+    if (eh < 0 || ew < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: filter larger than padded input", who);
+    g->Ho = eh / sh + 1; g->Wo = ew / sw + 1;
+    const long long xt_bytes = (long long)N * (H + 2LL * ph) * (W + 2LL * pw) * h->Cp;
+    if (xt_bytes >= 0x7fffff00LL || (long long)N * h->N * g->Ho * g->Wo > 0x7fffffffLL || (long long)N * g->Ho * g->Wo > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
+    return ADAPT_OK;
+}
+
+// x_dev == nullptr: the input copy is already in the handle's prepared workspace (written by the layer before);
+// next != nullptr: also write the output as next's input copy, quantised with s_next
+static int conv2d_layer(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W, int stride_h, int stride_w,
+                        int pad_h, int pad_w, int dil_h, int dil_w, float s_x, float s_out, const float *s_out_vec_dev,
+                        const float *bias_dev, const float *residual_dev, int act, const adapt_weights *next, float s_next, void *stream,
+                        const char *who) {
+    int rc = check_weights(h, 1, who);
+    if (rc) return rc;
+    ConvGeo g;
+    if ((rc = conv_geo(h, N, H, W, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, &g, who))) return rc;
+    if (N == 0) return ADAPT_OK;
+    const bool input_ready = x_dev == nullptr;
+    if (input_ready) {
+        const auto &ci = h->chain_in;
+        if (!ci.valid || ci.N != N || ci.H != H || ci.W != W || ci.sh != stride_h || ci.sw != stride_w || ci.ph != pad_h || ci.pw != pad_w ||
+            ci.dh != dil_h || ci.dw != dil_w)
+            return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: x_dev is NULL but the handle was not prepared for this geometry", who);
+    }
+    LayerIO io;
+    if ((rc = layer_io(&io, h, input_ready ? reinterpret_cast<const float *>(y_dev) : x_dev, y_dev, s_x, s_out, s_out_vec_dev, bias_dev, act, who)))
+        return rc;
+    if (input_ready) io.xf = nullptr;
+    io.resid = residual_dev;
+    if (residual_dev == y_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: residual_dev must not alias y_dev", who);
+    if (next) {
+        if ((rc = check_weights(next, 1, who))) return rc;
+        const auto &ci = next->chain_in;
+        if (!ci.valid || ci.N != N || ci.H != g.Ho || ci.W != g.Wo || next->Cin != h->N || !next->ws.ptr)
+            return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: the next layer was not prepared for this layer's output", who);
+        if (!(s_next > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: s_next must be > 0", who);
+        io.chain.buf = static_cast<int8_t *>(next->ws.ptr);
+        io.chain.xmajor = ci.xmajor; io.chain.Hp = ci.H + 2 * ci.ph; io.chain.Wp = ci.W + 2 * ci.pw; io.chain.Cp = next->Cp;
+        io.chain.ph = ci.ph; io.chain.pw = ci.pw;
+        io.chain.scale = s_next; io.chain.Q = (float)((1 << (next->bits - 1)) - 1); io.chain.mask = (1u << next->bits) - 1u;
+        io.chain_wo = (int)g.Wo;
+    }
+    return lines_conv2d(h->bits, h->storage, shape_of(h), h->dt_dev, nullptr, reinterpret_cast<int32_t *>(y_dev), N, H, W, (int)g.Ho,
+                        (int)g.Wo, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream, &h->ws, &io, h, input_ready);
+}
+
 int adapt_conv2d_layer_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W, int stride_h, int stride_w,
                            int pad_h, int pad_w, int dil_h, int dil_w, float s_x, float s_out, const float *s_out_vec_dev,
                            const float *bias_dev, const float *residual_dev, int act, void *stream) {
     const char *who = "adapt_conv2d_layer_f32";
+    if (!x_dev && N > 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
+    return conv2d_layer(h, x_dev, y_dev, N, H, W, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, s_x, s_out, s_out_vec_dev, bias_dev,
+                        residual_dev, act, nullptr, 1.0f, stream, who);
+}
+
+int adapt_conv2d_chain_prepare(const adapt_weights *h, int N, int H, int W, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h,
+                               int dil_w, void *stream) {
+    const char *who = "adapt_conv2d_chain_prepare";
     int rc = check_weights(h, 1, who);
     if (rc) return rc;
-    if (N < 0 || H < 1 || W < 1 || stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0 || dil_h < 1 || dil_w < 1)
-        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
-    const long long eh = (long long)H + 2LL * pad_h - (long long)dil_h * (h->kh - 1) - 1;
-    const long long ew = (long long)W + 2LL * pad_w - (long long)dil_w * (h->kw - 1) - 1;
-    if (eh < 0 || ew < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: filter larger than padded input", who);
-    const long long Ho = eh / stride_h + 1, Wo = ew / stride_w + 1;
+    ConvGeo g;
+    if ((rc = conv_geo(h, N, H, W, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, &g, who))) return rc;
+    h->chain_in.valid = false;
     if (N == 0) return ADAPT_OK;
-    LayerIO io;
-    if ((rc = layer_io(&io, h, x_dev, y_dev, s_x, s_out, s_out_vec_dev, bias_dev, act, who))) return rc;
-    io.resid = residual_dev;
-    if (residual_dev == y_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: residual_dev must not alias y_dev", who);
-    const long long xt_bytes = (long long)N * (H + 2LL * pad_h) * (W + 2LL * pad_w) * h->Cp;
-    if (xt_bytes >= 0x7fffff00LL || (long long)N * h->N * Ho * Wo > 0x7fffffffLL || (long long)N * Ho * Wo > 0x7fffffffLL)
-        return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
-    return lines_conv2d(h->bits, h->storage, shape_of(h), h->dt_dev, nullptr, reinterpret_cast<int32_t *>(y_dev), N, H, W, (int)Ho,
-                        (int)Wo, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream, &h->ws, &io, h);
+    // the layout decisions of lines_conv2d
+    const LinesShape q = shape_of(h);
+    const int M = (int)(N * g.Ho * g.Wo);
+    const int xmajor = (lines_rows_per_lane(M, q.n_tiles, q.k_cc(), q.k_taps()) == 8 && g.Wo % 4 == 0 && M % 8 == 0 && stride_w == 1 &&
+                        q.k_cc() % 4 == 0) ? 1 : 0;
+    const size_t xt_bytes = (size_t)N * (H + 2 * pad_h) * (W + 2 * pad_w) * q.Cp;
+    const size_t copy_bytes = ((xt_bytes + 64 + 255) / 256) * 256;
+    const size_t part_bytes = lines_partial_bytes(M, q.n_tiles, q.k_cc(), q.k_taps(), (size_t)M * q.N);
+    int8_t *xt = nullptr;
+    if ((rc = ws_get(&h->ws, copy_bytes + part_bytes, (hipStream_t)stream, (void **)&xt))) return rc;
+    adapt::fill_u32_kernel<<<ew_grid(copy_bytes / 4), 256, 0, (hipStream_t)stream>>>(reinterpret_cast<uint32_t *>(xt), 0u, copy_bytes / 4);
+    HIP_TRY(hipGetLastError());
+    auto &ci = h->chain_in;
+    ci.N = N; ci.H = H; ci.W = W; ci.sh = stride_h; ci.sw = stride_w; ci.ph = pad_h; ci.pw = pad_w; ci.dh = dil_h; ci.dw = dil_w;
+    ci.xmajor = xmajor; ci.valid = true;
+    return ADAPT_OK;
+}
+
+int adapt_conv2d_layer_chain_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W, int stride_h,
+                                 int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, float s_x, float s_out,
+                                 const float *s_out_vec_dev, const float *bias_dev, const float *residual_dev, int act,
+                                 const adapt_weights *next, float s_next, void *stream) {
+    return conv2d_layer(h, x_dev, y_dev, N, H, W, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, s_x, s_out, s_out_vec_dev, bias_dev,
+                        residual_dev, act, next, s_next, stream, "adapt_conv2d_layer_chain_f32");
 }
 
 int adapt_conv_transpose2d_layer_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W, int pad, float s_x,

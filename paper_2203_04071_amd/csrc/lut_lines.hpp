@@ -48,6 +48,24 @@ struct FastDiv {
     __device__ __forceinline__ uint32_t div(uint32_t n) const { return (uint32_t)(((uint64_t)n * M) >> k); }
 };
 
+// A layer's output written a second time as the NEXT convolution's input copy: quantised with that layer's activation
+// scale (the quantiser of Sec. III-A), as table line indices, at the element's place in the zero-padded x-major or
+// channel-last copy (see pad_channels_last_kernel) whose borders and padded channels were zeroed beforehand.  The next
+// layer then needs no copy kernel of its own.  buf == nullptr: nothing to do.
+struct ChainOut {
+    int8_t *buf;
+    int xmajor, Hp, Wp, Cp, ph, pw;
+    float scale, Q;
+    uint32_t mask;
+    // element (image, channel c, row oy, column ox) of the producing layer's fp32 output y
+    __device__ __forceinline__ void put(int img, int c, int oy, int ox, float y) const {
+        const uint32_t q = (uint32_t)quant1(y, scale, Q) & mask;
+        const size_t row = (size_t)img * Hp + oy + ph;
+        const size_t a = xmajor ? ((row * (Cp >> 2) + (c >> 2)) * Wp + ox + pw) * 4 + (c & 3) : (row * Wp + ox + pw) * Cp + c;
+        buf[a] = (int8_t)q;
+    }
+};
+
 struct LinesParams {
     const int8_t *xt;       // activations (see above)
     const uint4 *dt;        // derived tables [n_tiles][steps][2^b lines][8 columns] x 16 B
@@ -94,6 +112,7 @@ struct LinesParams {
     // of the padded copy, but the layer is defined over real (input, weight) pairs only; zsum[co][tap] = sum over the
     // input channels of T[0][w] is what such a tap added.  Output and input sizes, filter, stride, padding, and the
     // widths Ly / Lx of the output border in which some tap has no input pixel.
+    ChainOut chain;     // (ordinary convolutions with fused rescaling only: out_sy = Wo, out_sx = 1)
     const int32_t *zsum;
     FastDiv cv_s;                       // division by the stride
     int cv_Ho, cv_Wo, cv_H, cv_W, cv_kh, cv_kw, cv_pad, cv_Ly, cv_Lx;
@@ -393,10 +412,11 @@ __global__ void convt_border_fix_kernel(int32_t *__restrict__ out, const int32_t
 // In-place rescaling of a buffer of int32 sums into fp32 for the cases the product kernels cannot rescale themselves
 // (two-pass tables, transposed convolutions whose border terms are taken off afterwards, tanh outputs):
 // y = float(acc) * scale, + bias[c], then act (0 none, 1 max(y, 0), 2 tanh as in unary_kernel).
+// (chain: see ChainOut; chain_wo = width of the output, for the element's row and column)
 __global__ __launch_bounds__(EW_THREADS) void finish_inplace_kernel(int32_t *__restrict__ buf, size_t n, size_t channels, size_t inner,
                                                                     float scale, const float *__restrict__ scales,
                                                                     const float *__restrict__ bias, const float *__restrict__ resid,
-                                                                    int act) {
+                                                                    int act, ChainOut chain, int chain_wo) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
     for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
         const size_t ch = (i / inner) % channels;
@@ -406,6 +426,10 @@ __global__ __launch_bounds__(EW_THREADS) void finish_inplace_kernel(int32_t *__r
         if (act == 1) y = y > 0.0f ? y : 0.0f;
         else if (act == 2) y = tanh_spec(y);
         reinterpret_cast<float *>(buf)[i] = y;
+        if (chain.buf) {
+            const size_t pix = i % inner;
+            chain.put((int)(i / (inner * channels)), (int)ch, (int)(pix / chain_wo), (int)(pix % chain_wo), y);
+        }
     }
 }
 
@@ -416,7 +440,7 @@ __global__ __launch_bounds__(EW_THREADS) void reduce_partials_kernel(const int32
                                                                      size_t channels, size_t inner, float scale,
                                                                      const float *__restrict__ scales,
                                                                      const float *__restrict__ bias, const float *__restrict__ resid,
-                                                                     int act) {
+                                                                     int act, ChainOut chain, int chain_wo) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
     for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
         uint32_t v = 0;
@@ -431,6 +455,10 @@ __global__ __launch_bounds__(EW_THREADS) void reduce_partials_kernel(const int32
             if (act == 1) y = y > 0.0f ? y : 0.0f;
             else if (act == 2) y = tanh_spec(y);
             reinterpret_cast<float *>(out)[i] = y;
+            if (chain.buf) {
+                const size_t pix = i % inner;
+                chain.put((int)(i / (inner * channels)), (int)ch, (int)(pix / chain_wo), (int)(pix % chain_wo), y);
+            }
         } else {
             out[i] = (int32_t)v;
         }
@@ -708,8 +736,13 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_kernel(const LinesPar
             const int n = nt * 8 + (j >> 1) + 4 * t;
             if (n >= p.N) continue;
             int32_t *q = p.out + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
-            if (p.shift < 0) *q = (int32_t)finish_sum(p, w[i][t], n, (size_t)(q - p.out));
-            else *q = (int32_t)((uint32_t)*q + (w[i][t] << p.shift));
+            if (p.shift < 0) {
+                const uint32_t f = finish_sum(p, w[i][t], n, (size_t)(q - p.out));
+                *q = (int32_t)f;
+                if (p.chain.buf) p.chain.put(img, n, a, b, __uint_as_float(f));
+            } else {
+                *q = (int32_t)((uint32_t)*q + (w[i][t] << p.shift));
+            }
         }
     }
 }
@@ -1084,6 +1117,10 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
             uint32_t f[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) f[i] = p.shift < 0 ? finish_sum(p, w[i][t], n, (size_t)(q0 + i * sx - outp)) : w[i][t];
+            if (p.chain.buf) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) p.chain.put(img, n, a0, b0 + i, __uint_as_float(f[i]));
+            }
             if (p.shift < 0 && sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
                 *reinterpret_cast<uint4 *>(q0) = make_uint4(f[0], f[1], f[2], f[3]);
             } else {
@@ -1110,8 +1147,13 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
                 const int n = nt * 8 + (j >> 1) + 4 * t;
                 if (n >= p.N) continue;
                 int32_t *q = outp + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
-                if (p.shift < 0) *q = (int32_t)finish_sum(p, w[i][t], n, (size_t)(q - outp));
-                else *q = (int32_t)((uint32_t)*q + (w[i][t] << p.shift));
+                if (p.shift < 0) {
+                    const uint32_t f = finish_sum(p, w[i][t], n, (size_t)(q - outp));
+                    *q = (int32_t)f;
+                    if (p.chain.buf) p.chain.put(img, n, a, b, __uint_as_float(f));
+                } else {
+                    *q = (int32_t)((uint32_t)*q + (w[i][t] << p.shift));
+                }
             }
         }
     }

@@ -323,6 +323,10 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const Lin
         uint32_t f[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) f[i] = p.shift < 0 ? finish_sum<EXTRA>(p, w[i][t], n, (size_t)(q0 + i * sx - outp)) : w[i][t];
+        if (EXTRA && p.chain.buf) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) p.chain.put(img, n, a0, b0 + i, __uint_as_float(f[i]));
+        }
         if (p.shift < 0 && sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
             *reinterpret_cast<uint4 *>(q0) = make_uint4(f[0], f[1], f[2], f[3]);
         } else {

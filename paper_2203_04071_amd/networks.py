@@ -77,6 +77,17 @@ class ResNet20:
         self.fc_b = torch.from_numpy(cfg["fc_b"]).to(device)
         self.scales = None
         self.macs = None
+        self.chain = True           # frozen scales: every layer also writes the next layer's quantised input copy
+        self._prepared = None       # input shape the chained buffers were prepared for
+
+    def _prepare_chain(self, x):
+        """Fix the place and layout of every convolution's input copy (all but the first receive it from the layer before)."""
+        n, _, h, w = x.shape
+        for i, (cin, cout, st) in enumerate(self.plan):
+            if i > 0:
+                B.adapt_conv2d_chain_prepare(self.pws[i], n, h, w, (st, st), (1, 1))
+            h, w = (h + 2 - 3) // st + 1, (w + 2 - 3) // st + 1
+        self._prepared = tuple(x.shape)
 
     def _conv(self, i, x, used, keep, relu=False, residual=None):
         """conv (+ ReLU).  Once the scales are frozen and nobody asks for the integer sums, the layer runs as one
@@ -86,6 +97,17 @@ class ResNet20:
         if self.scales is not None and keep is None:
             s_x = self.scales[i]
             used.append(s_x)
+            if self.chain:
+                # the input copy of every layer but the first is already in place (the layer before wrote it, quantised with
+                # this layer's scale, from its epilogue); x is only needed for its shape
+                n, _, h, w = x.shape
+                ho, wo = (h + 2 - 3) // st + 1, (w + 2 - 3) // st + 1
+                out = torch.empty((n, self.plan[i][1], ho, wo), dtype=torch.float32, device=x.device)
+                last = i + 1 == len(self.plan)
+                return B.adapt_conv2d_layer_chain_f32(self.pws[i], x if i == 0 else None, s_x, _f(s_x) * _f(self.qws[i][1]), out, (st, st),
+                                                      (1, 1), act=B.ACT_RELU if relu else B.ACT_NONE, residual=residual,
+                                                      next_pw=None if last else self.pws[i + 1],
+                                                      s_next=1.0 if last else self.scales[i + 1], in_shape=(n, h, w))
             return B.adapt_conv2d_layer_f32(self.pws[i], x, s_x, _f(s_x) * _f(self.qws[i][1]), (st, st), (1, 1),
                                             act=B.ACT_RELU if relu else B.ACT_NONE, residual=residual)
         s_x = calibrated_scale(x, bits) if self.scales is None else self.scales[i]
@@ -102,6 +124,8 @@ class ResNet20:
 
     def forward(self, x, keep=None):
         used = []
+        if self.scales is not None and keep is None and self.chain and self._prepared != tuple(x.shape):
+            self._prepare_chain(x)
         x = self._conv(0, x, used, keep, relu=True)
         i = 1
         while i < len(self.plan):

@@ -1266,3 +1266,79 @@ def test_random_shapes_match_oracle(B, seed):
             bad.append(desc)
     assert not bad, bad
 
+
+# ------------------------------------------------------------------ chained convolution layers
+
+CHAIN_CASES = [
+    # N, C0, H, W, channels of three 3x3 layers, stride of the second, bits
+    (32, 64, 32, 32, (64, 64, 64), 1, 8),      # wide kernel producers and consumers (as configuration 2)
+    (16, 64, 8, 8, (64, 64, 64), 1, 8),        # inner dimension split over workgroups: the adding kernel writes the chain
+    (8, 16, 32, 32, (16, 16, 32), 2, 8),       # paired taps, x-major; then a stride-2 consumer with a channel-last copy
+    (4, 32, 16, 16, (32, 32, 32), 1, 8),       # 4 rows per lane, channel-last copies
+    (3, 5, 9, 7, (7, 12, 9), 1, 6),            # ragged everything: generic kernels
+    (2, 8, 12, 12, (24, 8, 16), 2, 7),
+]
+
+
+@pytest.mark.parametrize("case", CHAIN_CASES)
+def test_chained_conv_layers_match_unchained_and_oracle(B, case):
+    """Three convolution layers (bias + ReLU, residual on the last) where each layer writes the next layer's quantised,
+    padded input copy in its epilogue: fp32 outputs of every layer bit-identical to the oracle's layer-by-layer pass."""
+    N, C0, H, W, chans, s2, bits = case
+    rng = np.random.default_rng(sum(case[:4]) + bits)
+    lut = wl.make_lut(bits)
+    L = B.Lut(lut, bits)
+    x = rng.standard_normal((N, C0, H, W)).astype(np.float32)
+    cin = C0
+    ws, bs, strides = [], [], [1, s2, 1]
+    for c in chans:
+        ws.append(wl.random_i8(rng, (c, cin, 3, 3), bits, "gauss"))
+        bs.append(rng.standard_normal(c).astype(np.float32) * np.float32(0.1))
+        cin = c
+    # oracle pass, layer by layer, calibrating scales progressively
+    th = orc.host_threads()
+    acts, scales = [x], []
+    for i in range(3):
+        s_x = orc.scale_from_amax(orc.absmax(acts[-1]), bits)
+        scales.append(s_x)
+        acc = orc.approx_conv2d(lut, bits, orc.quantize(acts[-1], s_x, bits), ws[i], (strides[i],) * 2, (1, 1), threads=th)
+        n_, c_, h_, w_ = acc.shape
+        y = orc.dequant(acc, np.float32(s_x) * np.float32(0.01), n_, c_, h_ * w_, bs[i])
+        if i == 2 and chans[2] == chans[1]:
+            y = orc.add(y, acts[-1])
+        acts.append(np.maximum(y, 0))
+    pws = [B.adapt_weights_pack_conv2d(L, dev(w)) for w in ws]
+    shapes = [a.shape for a in acts]
+    for i in (1, 2):
+        B.adapt_conv2d_chain_prepare(pws[i], N, shapes[i][2], shapes[i][3], (strides[i],) * 2, (1, 1))
+    outs = [torch.empty(shapes[i + 1], dtype=torch.float32, device="cuda") for i in range(3)]
+    for rep in range(2):        # twice: the prepared buffers are reused
+        B.adapt_conv2d_layer_chain_f32(pws[0], dev(x), scales[0], np.float32(scales[0]) * np.float32(0.01), outs[0], (1, 1), (1, 1),
+                                       bias=dev(bs[0]), act=B.ACT_RELU, next_pw=pws[1], s_next=scales[1])
+        B.adapt_conv2d_layer_chain_f32(pws[1], None, scales[1], np.float32(scales[1]) * np.float32(0.01), outs[1], (s2, s2), (1, 1),
+                                       bias=dev(bs[1]), act=B.ACT_RELU, next_pw=pws[2], s_next=scales[2], in_shape=(N,) + shapes[1][2:])
+        B.adapt_conv2d_layer_chain_f32(pws[2], None, scales[2], np.float32(scales[2]) * np.float32(0.01), outs[2], (1, 1), (1, 1),
+                                       bias=dev(bs[2]), act=B.ACT_RELU, residual=outs[1] if chans[2] == chans[1] else None,
+                                       in_shape=(N,) + shapes[2][2:])
+        for i in range(3):
+            assert bits_equal(host(outs[i]), acts[i + 1]), (rep, i)
+
+
+def test_chain_refuses_unprepared_handles(B):
+    L = B.Lut(wl.make_lut(8), 8)
+    rng = np.random.default_rng(3)
+    p0 = B.adapt_weights_pack_conv2d(L, dev(wl.random_i8(rng, (8, 8, 3, 3), 8)))
+    p1 = B.adapt_weights_pack_conv2d(L, dev(wl.random_i8(rng, (8, 8, 3, 3), 8)))
+    x = torch.zeros((1, 8, 6, 6), device="cuda")
+    y = torch.empty((1, 8, 6, 6), device="cuda")
+    with pytest.raises(B.AdaptError) as e:
+        B.adapt_conv2d_layer_chain_f32(p0, x, 1.0, 1.0, y, (1, 1), (1, 1), next_pw=p1, s_next=1.0)
+    assert e.value.code == -1
+    with pytest.raises(B.AdaptError) as e:
+        B.adapt_conv2d_layer_chain_f32(p1, None, 1.0, 1.0, y, (1, 1), (1, 1), in_shape=(1, 6, 6))
+    assert e.value.code == -1
+    B.adapt_conv2d_chain_prepare(p1, 1, 6, 6, (1, 1), (1, 1))
+    B.adapt_conv2d_layer_f32(p1, torch.zeros((2, 8, 5, 5), device="cuda"), 1.0, 1.0, (1, 1), (1, 1))      # another geometry
+    with pytest.raises(B.AdaptError):
+        B.adapt_conv2d_layer_chain_f32(p1, None, 1.0, 1.0, y, (1, 1), (1, 1), in_shape=(1, 6, 6))
+
