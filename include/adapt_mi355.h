@@ -188,7 +188,7 @@ int adapt_approx_conv_transpose2d_packed(const adapt_weights *w, const int8_t *x
  *   next != NULL : y is ALSO written into the prepared workspace of `next` as its input copy, quantised with
  *                  s_next exactly as adapt_quantize_f32 would quantise y_dev (the output y_dev is still written).
  * `next` must have been prepared for N images of this layer's output size and have as many input channels as this
- * layer has output channels; otherwise ADAPT_ERR_INVALID_ARGUMENT.  An ordinary call on a prepared handle with
+ * layer has output channels, and must be another handle than `w`; otherwise ADAPT_ERR_INVALID_ARGUMENT.  An ordinary call on a prepared handle with
  * another geometry ends its prepared state.  Results are identical to the unchained calls. */
 int adapt_conv2d_chain_prepare(const adapt_weights *w, int N, int H, int W, int stride_h, int stride_w, int pad_h,
                                int pad_w, int dil_h, int dil_w, void *stream);

@@ -1530,6 +1530,7 @@ static int conv2d_layer(const adapt_weights *h, const float *x_dev, float *y_dev
     if (residual_dev == y_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: residual_dev must not alias y_dev", who);
     if (next) {
         if ((rc = check_weights(next, 1, who))) return rc;
+        if (next == h) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: a layer cannot chain into itself (one workspace per handle)", who);
         const auto &ci = next->chain_in;
         if (!ci.valid || ci.N != N || ci.H != g.Ho || ci.W != g.Wo || next->Cin != h->N || !next->ws.ptr)
             return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: the next layer was not prepared for this layer's output", who);
