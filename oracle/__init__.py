@@ -217,6 +217,14 @@ def percentile_from_histogram(counts, amax, num=999, den=1000) -> np.float32:
     return np.float32(out.value)
 
 
+def mse_from_histogram(counts, amax, bits) -> np.float32:
+    counts = np.ascontiguousarray(counts, dtype=np.uint32)
+    out = ctypes.c_float(0.0)
+    _check(lib().orc_mse_from_histogram(_p(counts), int(counts.size), ctypes.c_float(float(amax)), ctypes.c_int(bits),
+                                        ctypes.byref(out)), "mse_from_histogram")
+    return np.float32(out.value)
+
+
 def relu(x) -> np.ndarray:
     x = _f32(x)
     y = np.empty_like(x)

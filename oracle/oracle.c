@@ -348,6 +348,36 @@ int orc_percentile_from_histogram(const uint32_t *counts, int bins, float amax, 
     return ORC_OK;
 }
 
+/* calib_max by least squared quantisation error (Sec. III-A names MSE as an alternative calibrator without defining it;
+ * this is the reading of the design notes): every bin edge t_k = (k + 1) * width is a candidate range; with the scale
+ * s = t_k / Q (fp32, as the quantiser would use it) a value at the centre c_j = (j + 0.5) * width of bin j is
+ * reproduced as min(Q, rint(c_j / s)) * s; the candidate's error is sum_j counts[j] * (c_j - that)^2, all in fp64, j
+ * ascending; the first candidate with the smallest error wins. */
+int orc_mse_from_histogram(const uint32_t *counts, int bins, float amax, int bits, float *calib_max) {
+    if (!counts || !calib_max || bins < 1 || !(amax > 0.0f) || bits < 2 || bits > 16) return ORC_BAD_ARG;
+    const float width = amax / (float)bins;
+    const float Qf = (float)((1 << (bits - 1)) - 1);
+    const double Q = (double)Qf;
+    double best = 0.0;
+    int best_k = -1;
+    for (int k = 0; k < bins; ++k) {
+        const float t = (float)(k + 1) * width;
+        const double s = (double)(t / Qf);
+        double err = 0.0;
+        for (int j = 0; j < bins; ++j) {
+            if (!counts[j]) continue;
+            const double c = ((double)j + 0.5) * (double)width;
+            double q = rint(c / s);
+            if (q > Q) q = Q;
+            const double e = c - q * s;
+            err = err + (double)counts[j] * (e * e);
+        }
+        if (best_k < 0 || err < best) { best = err; best_k = k; }
+    }
+    *calib_max = (float)(best_k + 1) * width;
+    return ORC_OK;
+}
+
 /* ---------------------------------------------------------------------------
  * fp32 glue between approximate layers.  Each is one IEEE operation per element
  * in the stated order, so that the integers produced by the next quantiser are

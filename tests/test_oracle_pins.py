@@ -696,3 +696,50 @@ def test_oracle_reproduces_its_stored_small_cases():
     now = json.loads(json.dumps(mod.cases()))
     assert now == stored
 
+
+def test_mse_calibrator_against_direct_search_and_closed_cases():
+    """The least-squares range from the histogram equals the one found by literally quantising samples placed at the bin
+    centres and measuring their error for every candidate (a different route to the same number); a single far outlier is
+    clipped, a flat distribution is not, and scaling all counts changes nothing."""
+    rng = np.random.default_rng(17)
+    bins, bits = 64, 4
+    Q = 7.0
+    amax = np.float32(3.2)
+    width = np.float32(amax / np.float32(bins))
+    for trial in range(4):
+        counts = rng.integers(0, 6, bins).astype(np.uint32)
+        if trial == 1:
+            counts[:] = 0
+            counts[:6] = 1000
+            counts[-1] = 1                     # one outlier at the top
+        if trial == 2:
+            counts[:] = 5                      # flat
+        got = orc.mse_from_histogram(counts, amax, bits)
+        centres = (np.arange(bins) + 0.5) * np.float64(width)
+        samples = np.repeat(centres, counts)
+        errs = []
+        for k in range(bins):
+            t = np.float32(np.float32(k + 1) * width)
+            s = np.float64(np.float32(t / np.float32(Q)))
+            deq = np.minimum(np.rint(samples / s), Q) * s
+            errs.append(np.sum((samples - deq) ** 2))
+        errs = np.array(errs)
+        k_best = int(np.argmin(errs))
+        # the histogram form adds bin by bin, the sample form value by value: equal up to rounding, so compare the error of
+        # the chosen range with the best error instead of the index when two candidates are within rounding of each other
+        k_got = int(round(float(got) / float(width))) - 1
+        assert np.float32(np.float32(k_got + 1) * width) == got
+        assert errs[k_got] <= errs[k_best] * (1 + 1e-12) + 1e-300
+        if trial == 1:
+            assert got < amax * np.float32(0.5)      # the outlier is clipped
+        if trial == 2:
+            assert k_got >= bins * 3 // 4             # (almost) nothing worth clipping: a coarse grid trades a little clipping for a finer step
+        assert orc.mse_from_histogram(counts * np.uint32(7), amax, bits) == got
+    one = np.zeros(8, np.uint32)
+    one[2] = 9                                       # all values at the centre of bin 2: any range that reproduces it exactly wins;
+    got = orc.mse_from_histogram(one, 8.0, 8)        # centre 2.5, width 1: t = 5 gives s = 5/127 and q = 63.5 -> not exact
+    c = 2.5
+    errs = [(c - min(127.0, np.rint(c / np.float64(np.float32(np.float32(k + 1) / np.float32(127))))) * np.float64(np.float32(np.float32(k + 1) / np.float32(127)))) ** 2
+            for k in range(8)]
+    assert got == np.float32(int(np.argmin(errs)) + 1)
+
