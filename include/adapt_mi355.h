@@ -113,6 +113,11 @@ int adapt_histogram_abs_f32(const float *x_dev, size_t n, float amax, int bins, 
 /* calib_max_dev[0] for the fraction num / den (99.9 %: 999 / 1000; den <= 2^20) of the counted values */
 int adapt_percentile_from_histogram(const uint32_t *counts_dev, int bins, float amax, unsigned num, unsigned den,
                                     float *calib_max_dev, void *stream);
+/* calib_max_dev[0] by least squared quantisation error (Sec. III-A names an MSE calibrator as an alternative, without a
+ * definition; this one is: candidates are the bin edges t_k = (k + 1) * amax / bins; with the scale t_k / Q a value at
+ * the centre c_j of bin j is reproduced as min(Q, rint(c_j / s)) * s; the candidate's error is sum_j counts[j] *
+ * (c_j - that)^2 in fp64; the first candidate with the smallest error wins).  2 <= bits <= 16. */
+int adapt_mse_from_histogram(const uint32_t *counts_dev, int bins, float amax, int bits, float *calib_max_dev, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Approximate layers (Sec. III-B, IV): every inner-product term is one table entry.

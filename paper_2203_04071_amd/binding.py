@@ -24,7 +24,7 @@ EXPORTS = [
     "adapt_lut_create", "adapt_lut_destroy", "adapt_lut_info",
     "adapt_absmax_f32", "adapt_quantize_f32", "adapt_dequant_i32",
     "adapt_absmax_rows_f32", "adapt_quantize_rows_f32", "adapt_dequant_i32_per_channel",
-    "adapt_histogram_abs_f32", "adapt_percentile_from_histogram",
+    "adapt_histogram_abs_f32", "adapt_percentile_from_histogram", "adapt_mse_from_histogram",
     "adapt_approx_linear", "adapt_approx_conv2d", "adapt_approx_conv_transpose2d",
     "adapt_weights_pack_linear", "adapt_weights_pack_conv2d", "adapt_weights_pack_conv_transpose2d",
     "adapt_weights_destroy",
@@ -70,6 +70,7 @@ def load() -> ctypes.CDLL:
     L.adapt_dequant_i32_per_channel.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp]
     L.adapt_histogram_abs_f32.argtypes = [vp, sz, f32, i32, vp, vp]
     L.adapt_percentile_from_histogram.argtypes = [vp, i32, f32, ctypes.c_uint, ctypes.c_uint, vp, vp]
+    L.adapt_mse_from_histogram.argtypes = [vp, i32, f32, i32, vp, vp]
     L.adapt_quantize_f32.argtypes = [vp, vp, sz, f32, i32, vp]
     L.adapt_lut16_create.argtypes = [ctypes.POINTER(vp), i32, vp]
     L.adapt_lut16_create_from_func.argtypes = [ctypes.POINTER(vp), i32, i32, i32]
@@ -630,3 +631,12 @@ def adapt_percentile_from_histogram(counts, amax, num=999, den=1000, out=None, s
     _chk(load().adapt_percentile_from_histogram(_ptr(counts, torch.int32), counts.numel(), float(amax), num, den,
                                                 _ptr(out, torch.float32), _stream(stream)))
     return out
+
+
+def adapt_mse_from_histogram(counts, amax, bits, out=None, stream=None):
+    if out is None:
+        out = torch.empty((1,), dtype=torch.float32, device=counts.device)
+    _chk(load().adapt_mse_from_histogram(_ptr(counts, torch.int32), counts.numel(), float(amax), bits, _ptr(out, torch.float32),
+                                         _stream(stream)))
+    return out
+

@@ -1439,6 +1439,26 @@ int adapt_percentile_from_histogram(const uint32_t *counts_dev, int bins, float 
     return ADAPT_OK;
 }
 
+int adapt_mse_from_histogram(const uint32_t *counts_dev, int bins, float amax, int bits, float *calib_max_dev, void *stream) {
+    if (bins < 1 || bins > 4096) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_mse_from_histogram: bins=%d not in [1,4096]", bins);
+    if (!(amax > 0.0f) || bits < 2 || bits > 16) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_mse_from_histogram: need amax > 0 and 2 <= bits <= 16");
+    if (!counts_dev || !calib_max_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_mse_from_histogram: NULL pointer");
+    hipStream_t s = (hipStream_t)stream;
+    double *err = nullptr;
+    HIP_TRY(hipMallocAsync((void **)&err, (size_t)bins * sizeof(double), s));
+    const float width = amax / (float)bins;
+    adapt::mse_candidates_kernel<<<(unsigned)((bins + 255) / 256), 256, 0, s>>>(counts_dev, bins, width, (float)((1 << (bits - 1)) - 1), err);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) {
+        adapt::mse_pick_kernel<<<1, 64, 0, s>>>(err, bins, width, calib_max_dev);
+        e = hipGetLastError();
+    }
+    hipError_t fe = hipFreeAsync(err, s);
+    if (e != hipSuccess) return fail(ADAPT_ERR_HIP, "adapt_mse_from_histogram: %s", hipGetErrorString(e));
+    if (fe != hipSuccess) return fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
+    return ADAPT_OK;
+}
+
 /* ------------------------------------------------------------------ whole layers, fp32 in and out */
 
 static int layer_io(LayerIO *io, const adapt_weights *h, const float *x_dev, const float *y_dev, float s_x, float s_out,

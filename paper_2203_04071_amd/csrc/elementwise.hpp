@@ -157,6 +157,42 @@ __global__ void percentile_kernel(const uint32_t *__restrict__ counts, int bins,
     out[0] = (float)(k + 1) * width;
 }
 
+// Least-squares range from the histogram: candidate k has range t_k = (k + 1) * width and scale s = t_k / Q (fp32); a
+// value at the centre c_j = (j + 0.5) * width of bin j is reproduced as min(Q, rint(c_j / s)) * s; err[k] = sum_j
+// counts[j] * (c_j - that)^2 in fp64, j ascending, every operation rounded on its own (the library is compiled without
+// contraction).  One thread per candidate.
+__global__ __launch_bounds__(256) void mse_candidates_kernel(const uint32_t *__restrict__ counts, int bins, float width, float Qf,
+                                                             double *__restrict__ err) {
+    __shared__ uint32_t cnt[4096];
+    for (int j = threadIdx.x; j < bins; j += 256) cnt[j] = counts[j];
+    __syncthreads();
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    if (k >= bins) return;
+    const float t = (float)(k + 1) * width;
+    const double s = (double)(t / Qf), Q = (double)Qf;
+    double e2 = 0.0;
+    for (int j = 0; j < bins; ++j) {
+        const uint32_t n = cnt[j];
+        if (!n) continue;
+        const double c = ((double)j + 0.5) * (double)width;
+        double q = rint(c / s);
+        if (q > Q) q = Q;
+        const double e = c - q * s;
+        e2 = e2 + (double)n * (e * e);
+    }
+    err[k] = e2;
+}
+
+// the first candidate with the smallest error: calib_max = (k + 1) * width
+__global__ void mse_pick_kernel(const double *__restrict__ err, int bins, float width, float *__restrict__ out) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    int best_k = 0;
+    double best = err[0];
+    for (int k = 1; k < bins; ++k)
+        if (err[k] < best) { best = err[k]; best_k = k; }
+    out[0] = (float)(best_k + 1) * width;
+}
+
 // y = float(acc) * scale (+ bias[c]); channel of flat index i is (i / inner) % channels
 __global__ __launch_bounds__(EW_THREADS) void dequant_kernel(const int32_t *__restrict__ acc, float *__restrict__ y,
                                                              size_t n, size_t channels, size_t inner, float scale,

@@ -914,6 +914,10 @@ def test_histogram_and_percentile_bit_exact(B, n, bins):
     for num, den in ((999, 1000), (1, 2), (1000, 1000), (0, 7)):
         got = host(B.adapt_percentile_from_histogram(counts, amax, num, den))[0]
         assert np.float32(got) == orc.percentile_from_histogram(want2, amax, num, den), (num, den)
+    if bins <= 2048:        # (the oracle's search is quadratic in the bins)
+        for bits in (4, 8, 12):
+            got = host(B.adapt_mse_from_histogram(counts, amax, bits))[0]
+            assert np.float32(got) == orc.mse_from_histogram(want2, amax, bits), bits
 
 
 def test_conv_layer_with_per_channel_weights_and_percentile_activations(B):
