@@ -184,6 +184,19 @@ int adapt_approx_conv2d_packed(const adapt_weights *w, const int8_t *x_dev, int3
 int adapt_approx_conv_transpose2d_packed(const adapt_weights *w, const int8_t *x_dev, int32_t *acc_dev, int N, int H, int W,
                                          int pad, void *stream);
 
+/* A grouped convolution whose groups have fewer than 8 output channels (depthwise: groups = Cin, the first half of the
+ * separable convolution, eq. (1)) as one call and one kernel: x is quantised with s_x while it is staged, the sums are
+ * rescaled as in adapt_conv2d_layer_f32 (s_out or s_out_vec_dev, bias, act) and written to y_dev (fp32 [N][Cout][Ho][Wo];
+ * may be NULL when `next` is given), and, when `next` != NULL (a prepared conv2d handle, e.g. the pointwise half), also
+ * as next's quantised input copy as in adapt_conv2d_layer_chain_f32.  w_dev int8 [Cout][Cin/groups][kh][kw].  Shapes
+ * whose input rows do not fit the kernel's staging buffer, other group sizes and two-pass tables return
+ * ADAPT_ERR_UNSUPPORTED (use the separate calls). */
+int adapt_conv2d_grouped_layer_f32(const adapt_lut *lut, const float *x_dev, const int8_t *w_dev, float *y_dev, int N,
+                                   int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w,
+                                   int pad_h, int pad_w, int dil_h, int dil_w, int groups, float s_x, float s_out,
+                                   const float *s_out_vec_dev, const float *bias_dev, int act,
+                                   const adapt_weights *next, float s_next, void *stream);
+
 /* Chained convolution layers (Sec. III-A / IV: quantise -> table-lookup layer -> dequantise per layer; here the
  * re-quantisation for the NEXT layer happens in this layer's epilogue).  adapt_conv2d_chain_prepare fixes the place
  * and layout of `h`'s quantised, zero-padded input copy for one input geometry and zeroes it (borders and padded

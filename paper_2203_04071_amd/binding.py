@@ -30,7 +30,7 @@ EXPORTS = [
     "adapt_weights_destroy",
     "adapt_approx_linear_packed", "adapt_approx_conv2d_packed", "adapt_approx_conv_transpose2d_packed",
     "adapt_linear_layer_f32", "adapt_conv2d_layer_f32", "adapt_conv_transpose2d_layer_f32",
-    "adapt_conv2d_chain_prepare", "adapt_conv2d_layer_chain_f32",
+    "adapt_conv2d_chain_prepare", "adapt_conv2d_layer_chain_f32", "adapt_conv2d_grouped_layer_f32",
     "adapt_relu_f32", "adapt_add_f32", "adapt_avgpool_hw_f32", "adapt_shortcut_a_f32",
     "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32", "adapt_lstm_cell_q_f32", "adapt_lstm_step_f32", "adapt_gru_cell_f32", "adapt_rnn_cell_f32",
     "adapt_lut16_create", "adapt_lut16_create_from_func", "adapt_lut16_destroy", "adapt_lut16_bits", "adapt_quantize_i16_f32",
@@ -93,6 +93,7 @@ def load() -> ctypes.CDLL:
     L.adapt_linear_layer_f32.argtypes = [vp, vp, vp, i32, f32, f32, vp, vp, i32, vp]
     L.adapt_conv2d_layer_f32.argtypes = [vp, vp, vp] + [i32] * 9 + [f32, f32, vp, vp, vp, i32, vp]
     L.adapt_conv2d_chain_prepare.argtypes = [vp] + [i32] * 9 + [vp]
+    L.adapt_conv2d_grouped_layer_f32.argtypes = [vp, vp, vp, vp] + [i32] * 14 + [f32, f32, vp, vp, i32, vp, f32, vp]
     L.adapt_conv2d_layer_chain_f32.argtypes = [vp, vp, vp] + [i32] * 9 + [f32, f32, vp, vp, vp, i32, vp, f32, vp]
     L.adapt_conv_transpose2d_layer_f32.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, f32, vp, vp, i32, vp]
     L.adapt_approx_linear_packed.argtypes = [vp, vp, vp, i32, vp]
@@ -563,6 +564,22 @@ def adapt_conv2d_layer_chain_f32(pw: PackedWeights, x, s_x, s_out, out, stride=(
                                              pad[0], pad[1], dil[0], dil[1], float(s_x), s_scalar, s_vec, _ptr(bias, torch.float32),
                                              _ptr(residual, torch.float32), act, next_pw.handle if next_pw is not None else None,
                                              float(s_next), _stream(stream)))
+    return out
+
+
+def adapt_conv2d_grouped_layer_f32(lut: Lut, x, w, s_x, s_out, stride=(1, 1), pad=(0, 0), dil=(1, 1), groups=1, bias=None, act=ACT_NONE,
+                                   out=None, want_out=True, next_pw: PackedWeights = None, s_next: float = 1.0, stream=None):
+    """Depthwise-style grouped convolution as one kernel (fp32 in; fp32 out and / or the next layer's input copy)."""
+    N, Cin, H, W = x.shape
+    Cout, cg, kh, kw = w.shape
+    if out is None and want_out:
+        Ho, Wo = conv_out_hw(H, W, kh, kw, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1])
+        out = torch.empty((N, Cout, Ho, Wo), dtype=torch.float32, device=x.device)
+    s_scalar, s_vec = _scales(s_out)
+    _chk(load().adapt_conv2d_grouped_layer_f32(lut.handle, _ptr(x, torch.float32), _ptr(w, torch.int8), _ptr(out, torch.float32), N, Cin,
+                                               H, W, Cout, kh, kw, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1], groups,
+                                               float(s_x), s_scalar, s_vec, _ptr(bias, torch.float32), act,
+                                               next_pw.handle if next_pw is not None else None, float(s_next), _stream(stream)))
     return out
 
 

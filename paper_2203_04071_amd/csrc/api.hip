@@ -403,10 +403,17 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
 }
 
 // Grouped convolution with fewer than 8 output channels per group (depthwise and its relatives): direct form
+// io: whole-layer form (fp32 activations in, rescaled fp32 / chained output): only the tiled kernel has it, so the call is
+// refused with ADAPT_ERR_UNSUPPORTED when the shape does not take that kernel
 int run_grouped(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *out, int N, int Cin, int H, int W, int Cout, int Ho,
-                int Wo, int kh, int kw, int sh, int sw, int ph, int pw, int dh, int dw, int groups, hipStream_t s) {
+                int Wo, int kh, int kw, int sh, int sw, int ph, int pw, int dh, int dw, int groups, hipStream_t s,
+                const LayerIO *io = nullptr) {
     adapt::GroupedParams p;
     p.x = x; p.w = w; p.out = out; p.img_bytes = lut->img_bytes;
+    p.xf = io ? io->xf : nullptr; p.qscale = io ? io->s_x : 1.0f; p.qQ = io ? io->Q : 1.0f;
+    p.deq = io ? io->deq : 0; p.act = io ? io->act : 0; p.scale = io ? io->s_out : 1.0f;
+    p.scales = io ? io->s_out_vec : nullptr; p.bias = io ? io->bias : nullptr;
+    p.chain = io ? io->chain : adapt::ChainOut{};
     p.Cin = Cin; p.H = H; p.W = W; p.Cout = Cout; p.Ho = Ho; p.Wo = Wo; p.kh = kh; p.kw = kw;
     p.sh = sh; p.sw = sw; p.ph = ph; p.pw = pw; p.dh = dh; p.dw = dw;
     p.cg = Cin / groups; p.og = Cout / groups;
@@ -420,14 +427,28 @@ int run_grouped(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t 
     }
     // tiled form: the input region of a tile and the tap words of its groups sit in LDS next to the table
     const int taps = kh * kw;
-    const long long Wr = (long long)(Wo - 1) * sw + (long long)(kw - 1) * dw + 1;
+    long long Wr = (long long)(Wo - 1) * sw + (long long)(kw - 1) * dw + 1;
+    // strips of four output pixels (see the kernel): filter widths and strides it is instantiated for; the region rows
+    // then cover whole strips and are a multiple of 4 bytes wide
+    int variant = 0;
+    if (dw == 1 && (kw == 3 || kw == 5) && (sw == 1 || sw == 2) && lut->img_bytes % 4 == 0) {
+        variant = (kw == 3 ? 1 : 2) + (sw == 2 ? 2 : 0);
+        const long long Wo4 = (Wo + 3) / 4;
+        Wr = ((4 * Wo4 - 1) * sw + kw + 3) / 4 * 4;
+    }
     const long long rows_min = (long long)(kh - 1) * dh + 1;
     const long long cap = (long long)adapt::GROUPED_PF * adapt::ROWS_THREADS;
+    if (variant && p.cg * rows_min * Wr > cap) {        // the wider rows do not fit: pixel by pixel
+        variant = 0;
+        Wr = (long long)(Wo - 1) * sw + (long long)(kw - 1) * dw + 1;
+    }
     const long long wgroup = (long long)p.og * p.cg * taps;             // tap words of one group
     const size_t wl_bytes = (size_t)adapt::ROWS_THREADS * 4;
     const bool tiled = wgroup <= adapt::ROWS_THREADS && p.cg * rows_min * Wr <= cap &&
                        (size_t)lut->img_bytes + wl_bytes + (size_t)cap <= 160 * 1024;
     size_t blocks, lds;
+    if (io && (!tiled || lut->storage != 0))
+        return fail(ADAPT_ERR_UNSUPPORTED, "grouped layer call: this shape or table does not take the tiled kernel");
     if (tiled) {
         // rows per tile: as many as the region buffer holds for one group; then as many groups as still fit; both
         // reduced again while the tiles would not cover the chip twice
@@ -441,8 +462,20 @@ int run_grouped(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t 
         auto tiles = [&](long long r, long long g) { return (long long)N * ((groups + g - 1) / g) * ((Ho + r - 1) / r); };
         while (gt > 1 && tiles(ro, gt) < 2LL * cu) gt = (gt + 1) / 2;
         while (ro > 1 && tiles(ro, gt) < 2LL * cu) ro = (ro + 1) / 2;
+        // a tile whose channels are whole quads writes the next layer's copy a word at a time
+        const long long quad = p.og % 4 == 0 ? 1 : (p.og % 2 == 0 ? 2 : 4);
+        if (p.chain.buf && gt > quad) gt -= gt % quad;
         if (tiles(ro, gt) > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "adapt_approx_conv2d: too many tiles");
         p.gt = (int)gt;
+        {
+            // work items of (channel slot, pixel): enough slots that a tile has work for every lane
+            const long long chans = gt * p.og, npix = ro * Wo;
+            long long cpl = npix >= adapt::ROWS_THREADS ? chans : chans * npix / adapt::ROWS_THREADS;
+            if (cpl < 1) cpl = 1;
+            if (p.chain.buf && chans % 4 == 0) cpl = cpl < 4 ? 4 : cpl / 4 * 4;
+            p.cpl = (int)cpl;
+        }
+        p.chain4 = p.chain.buf && (gt * p.og) % 4 == 0 && p.chain.Cp % 4 == 0;
         p.ro = (int)ro; p.n_chunks = (int)((Ho + ro - 1) / ro);
         p.rows_in = (int)rows_in(ro); p.Wr = (int)Wr;
         p.tile_elems = (int)gt * p.cg * p.rows_in * p.Wr;
@@ -452,21 +485,31 @@ int run_grouped(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t 
         lds = (size_t)lut->img_bytes + wl_bytes + (size_t)((p.tile_elems + 15) / 16 * 16);
     } else {
         // one workgroup per compute unit at most (the table image fills its LDS), fewer when there is little to do
+        p.chain4 = 0; p.cpl = 1;
         p.gt = p.ro = p.n_chunks = p.rows_in = p.Wr = p.tile_elems = p.wl_bytes = p.ntiles = 0;
         blocks = (p.total + adapt::ROWS_THREADS * 4 - 1) / (adapt::ROWS_THREADS * 4);
         if (blocks > (size_t)cu) blocks = (size_t)cu;
         lds = (size_t)lut->img_bytes;
     }
-    static size_t configured[2][2] = {{0, 0}, {0, 0}};
+    if (!tiled) variant = 0;
+    using kern_t = void (*)(const adapt::GroupedParams);
+    static const kern_t tiled_kernels[5][2] = {
+        {adapt::lut_grouped_tiled_kernel<false, 0, 1>, adapt::lut_grouped_tiled_kernel<true, 0, 1>},
+        {adapt::lut_grouped_tiled_kernel<false, 3, 1>, adapt::lut_grouped_tiled_kernel<true, 3, 1>},
+        {adapt::lut_grouped_tiled_kernel<false, 5, 1>, adapt::lut_grouped_tiled_kernel<true, 5, 1>},
+        {adapt::lut_grouped_tiled_kernel<false, 3, 2>, adapt::lut_grouped_tiled_kernel<true, 3, 2>},
+        {adapt::lut_grouped_tiled_kernel<false, 5, 2>, adapt::lut_grouped_tiled_kernel<true, 5, 2>},
+    };
+    static size_t configured[6][2] = {};
     for (int half = 0; half <= lut->storage; ++half) {
         p.img = lut->img_dev[half];
         p.shift = half == 0 ? -1 : 16;
         const bool sgn = (lut->storage == 0) || half == 1;
-        auto kern = tiled ? (sgn ? adapt::lut_grouped_tiled_kernel<true> : adapt::lut_grouped_tiled_kernel<false>)
-                          : (sgn ? adapt::lut_grouped_kernel<true> : adapt::lut_grouped_kernel<false>);
-        if (lds > configured[tiled][sgn]) {
+        const kern_t kern = tiled ? tiled_kernels[variant][sgn] : (sgn ? adapt::lut_grouped_kernel<true> : adapt::lut_grouped_kernel<false>);
+        const int slot = tiled ? variant : 5;
+        if (lds > configured[slot][sgn]) {
             HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            configured[tiled][sgn] = lds;
+            configured[slot][sgn] = lds;
         }
         kern<<<(unsigned)blocks, adapt::ROWS_THREADS, lds, s>>>(p);
         HIP_TRY(hipGetLastError());
@@ -1607,6 +1650,47 @@ int adapt_conv2d_layer_chain_f32(const adapt_weights *h, const float *x_dev, flo
                                  const adapt_weights *next, float s_next, void *stream) {
     return conv2d_layer(h, x_dev, y_dev, N, H, W, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, s_x, s_out, s_out_vec_dev, bias_dev,
                         residual_dev, act, next, s_next, stream, "adapt_conv2d_layer_chain_f32");
+}
+
+int adapt_conv2d_grouped_layer_f32(const adapt_lut *lut, const float *x_dev, const int8_t *w_dev, float *y_dev, int N, int Cin, int H,
+                                   int W, int Cout, int kh, int kw, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h,
+                                   int dil_w, int groups, float s_x, float s_out, const float *s_out_vec_dev, const float *bias_dev,
+                                   int act, const adapt_weights *next, float s_next, void *stream) {
+    const char *who = "adapt_conv2d_grouped_layer_f32";
+    int rc = check_lut(lut, who);
+    if (rc) return rc;
+    if (N < 0 || Cin < 1 || H < 1 || W < 1 || Cout < 1 || kh < 1 || kw < 1 || stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0 ||
+        dil_h < 1 || dil_w < 1 || groups < 1)
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
+    if (Cin % groups || Cout % groups) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: channels not divisible by groups", who);
+    if (act < 0 || act > 2) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: act=%d not in {0, 1, 2}", who, act);
+    if (!(s_x > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: s_x must be > 0", who);
+    const long long eh = (long long)H + 2LL * pad_h - (long long)dil_h * (kh - 1) - 1, ew = (long long)W + 2LL * pad_w - (long long)dil_w * (kw - 1) - 1;
+    if (eh < 0 || ew < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: filter larger than padded input", who);
+    const long long Ho = eh / stride_h + 1, Wo = ew / stride_w + 1;
+    if (N == 0) return ADAPT_OK;
+    if (!x_dev || !w_dev || (!y_dev && !next)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
+    if ((long long)N * Cout * Ho * Wo > 0x7fffffffLL || (long long)N * Cin * H * W > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
+    if (groups == 1 || Cout / groups >= 8)
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: only groups with fewer than 8 output channels each (depthwise and relatives)", who);
+    LayerIO io;
+    io.xf = x_dev; io.s_x = s_x; io.Q = (float)((1 << (lut->bits - 1)) - 1);
+    io.deq = 1; io.act = act; io.s_out = s_out; io.s_out_vec = s_out_vec_dev; io.bias = bias_dev;
+    if (next) {
+        if ((rc = check_weights(next, 1, who))) return rc;
+        const auto &ci = next->chain_in;
+        if (!ci.valid || ci.N != N || ci.H != Ho || ci.W != Wo || next->Cin != Cout || !next->ws.ptr)
+            return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: the next layer was not prepared for this layer's output", who);
+        if (!(s_next > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: s_next must be > 0", who);
+        io.chain.buf = static_cast<int8_t *>(next->ws.ptr);
+        io.chain.xmajor = ci.xmajor; io.chain.Hp = ci.H + 2 * ci.ph; io.chain.Wp = ci.W + 2 * ci.pw; io.chain.Cp = next->Cp;
+        io.chain.ph = ci.ph; io.chain.pw = ci.pw;
+        io.chain.scale = s_next; io.chain.Q = (float)((1 << (next->bits - 1)) - 1); io.chain.mask = (1u << next->bits) - 1u;
+        io.chain_wo = (int)Wo;
+    }
+    return run_grouped(lut, nullptr, w_dev, reinterpret_cast<int32_t *>(y_dev), N, Cin, H, W, Cout, (int)Ho, (int)Wo, kh, kw, stride_h,
+                       stride_w, pad_h, pad_w, dil_h, dil_w, groups, (hipStream_t)stream, &io);
 }
 
 int adapt_conv_transpose2d_layer_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W, int pad, float s_x,

@@ -9,6 +9,7 @@
 // the size of the grid; the table is staged once per workgroup and serves many planes.
 // Padded taps are looked up with activation 0 like everywhere else (they are entries of the expanded input matrix).
 #pragma once
+#include "lut_lines.hpp"
 #include "lut_rows.hpp"
 
 namespace adapt {
@@ -32,6 +33,18 @@ struct GroupedParams {
     int tile_elems;         // gt * cg * rows_in * Wr  (<= GROUPED_PF * ROWS_THREADS)
     int wl_bytes;           // LDS bytes of the gt * og * cg * kh * kw (<= ROWS_THREADS) tap words (multiple of 16)
     int ntiles;             // N * ceil(groups / gt) * n_chunks
+    // whole-layer form (tiled kernel, single-pass tables): xf != nullptr reads fp32 activations and quantises them while
+    // the tile is written (the quantiser of Sec. III-A with scale qscale); deq != 0 turns the sums into fp32
+    // y = float(acc) * scale (or scales[co]), + bias[co], then ReLU (act 1) or tanh (act 2), stored at `out` unless that is
+    // nullptr; chain: y also becomes the next convolution's quantised input copy (see ChainOut)
+    const float *xf;
+    float qscale, qQ;
+    int deq, act;
+    float scale;
+    const float *scales, *bias;
+    ChainOut chain;
+    int cpl;                // output channels per work item of the tiled kernel (a multiple of 4 when chain4)
+    int chain4;             // every tile starts at a channel that is a multiple of 4 and the copy's rows are whole words
 };
 
 constexpr int GROUPED_CHUNK = 9;
@@ -97,11 +110,17 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_grouped_kernel(const Grouped
 constexpr int GROUPED_PF = 8;               // input elements a lane prefetches per tile (region <= 8 KB)
 constexpr int GROUPED_TOFF_SHIFT = 18;      // row offsets stay below 2^18 (255 rows of 516 bytes), tap offsets below 2^14
 
-template <bool SIGNED>
+//
+// KW > 0 (filter width KW, horizontal stride SW, no horizontal dilation; region rows a multiple of 4 bytes wide): a work
+// item is a strip of FOUR adjacent output pixels of one channel.  The 3 SW + KW activation bytes that a filter row
+// needs for the strip are read as aligned words, once, and the filter row's tap words once, so an item issues one LDS
+// read per lookup plus a handful per filter row instead of three per lookup — the kernel is bound by the number of
+// LDS instructions.  When the layer also writes the next layer's input copy, the four lanes of a quad hold the same
+// strip of four consecutive channels and exchange their codes, so that each stores one pixel's four channels as a word.
+template <bool SIGNED, int KW, int SW>
 __global__ __launch_bounds__(ROWS_THREADS) void lut_grouped_tiled_kernel(const GroupedParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
-    stage_table(smem, p.img, p.img_bytes, tid);
     uint32_t *wl = reinterpret_cast<uint32_t *>(smem + p.img_bytes);        // [gt * og][cg][taps] words of the tile's groups
     unsigned char *tl = smem + p.img_bytes + p.wl_bytes;                     // [gt * cg][rows_in][Wr] column indices
     const int groups = p.Cin / p.cg, taps = p.kh * p.kw, K = p.cg * taps;
@@ -125,9 +144,20 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_grouped_tiled_kernel(const G
         const int ky = tp / p.kw, kx = tp - ky * p.kw;
         my_toff = (uint32_t)(((gi * p.cg + ci) * p.rows_in + ky * p.dh) * p.Wr + kx * p.dw) << GROUPED_TOFF_SHIFT;
     }
-    const int pix0_r = tid / p.Wo, pix0_x = tid - pix0_r * p.Wo;            // first output pixel of this lane in a tile
-    const int step_r = ROWS_THREADS / p.Wo, step_x = ROWS_THREADS - step_r * p.Wo;
+    // work items of a tile: (slot of cpl consecutive output channels, output row, output column), column fastest; lane
+    // tid takes items tid, tid + 1024, ...: its first item and the step, decomposed once
     const int npix = p.ro * p.Wo;
+    const int it0_s = tid / npix, it0_r = (tid - it0_s * npix) / p.Wo, it0_x = tid - it0_s * npix - it0_r * p.Wo;
+    const int d_s = ROWS_THREADS / npix, d_r = (ROWS_THREADS - d_s * npix) / p.Wo, d_x = ROWS_THREADS - d_s * npix - d_r * p.Wo;
+
+    // strips (KW > 0): items (slot, row, strip of 4 columns), strip fastest; with the quad exchange the 4 lanes of a quad
+    // share an item and differ in the channel (slot = 4 channels), otherwise slot = channel
+    const int q4 = KW > 0 && p.chain4 ? 1 : 0, cl = q4 ? tid & 3 : 0;
+    const int Wo4 = (p.Wo + 3) >> 2, nstrip = p.ro * Wo4;
+    const int s_tid = q4 ? tid >> 2 : tid, s_step = q4 ? ROWS_THREADS >> 2 : ROWS_THREADS;
+    const int st0_s = s_tid / nstrip, st0_r = (s_tid - st0_s * nstrip) / Wo4, st0_x = s_tid - st0_s * nstrip - st0_r * Wo4;
+    const int sd_s = s_step / nstrip, sd_r = (s_step - sd_s * nstrip) / Wo4, sd_x = s_step - sd_s * nstrip - sd_r * Wo4;
+    const bool vec_out = (p.Wo & 3) == 0 && (reinterpret_cast<uintptr_t>(p.out) & 15u) == 0;                                   // 4 outputs of a strip = one aligned 16-byte store
 
     // Prefetch: the byte loads are issued from inline assembly and retired by an explicit wait just before their values
     // are written to LDS, one tile later.  (Issued by the compiler they would be waited for at the first instruction
@@ -148,8 +178,13 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_grouped_tiled_kernel(const G
         for (int u = 0; u < GROUPED_PF; ++u) {
             const bool in = tid + u * ROWS_THREADS < elems && (unsigned)(iy_start + el_r[u]) < (unsigned)p.H &&
                             (unsigned)el_x[u] < (unsigned)p.W;
-            const int8_t *src = xg + (in ? el_off[u] + shift_off : 0);
-            asm volatile("global_load_sbyte %0, %1, off" : "=v"(pre[u]) : "v"(src) : "memory");
+            if (p.xf) {         // (uniform)
+                const float *src = p.xf + ((size_t)n * p.Cin + (size_t)gb * p.gt * p.cg) * p.H * p.W + (in ? el_off[u] + shift_off : 0);
+                asm volatile("global_load_dword %0, %1, off" : "=v"(pre[u]) : "v"(src) : "memory");
+            } else {
+                const int8_t *src = xg + (in ? el_off[u] + shift_off : 0);
+                asm volatile("global_load_sbyte %0, %1, off" : "=v"(pre[u]) : "v"(src) : "memory");
+            }
             pre_in |= in ? 1u << u : 0u;
         }
         const int8_t *wsrc = p.w + (tid < words ? (size_t)gb * p.gt * p.og * K + tid : 0);
@@ -164,8 +199,10 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_grouped_tiled_kernel(const G
                      : "memory");
 #pragma unroll
         for (int u = 0; u < GROUPED_PF; ++u)
-            if (tid + u * ROWS_THREADS < p.tile_elems)
-                tl[tid + u * ROWS_THREADS] = (unsigned char)((pre_in >> u) & 1u ? ((pre[u] + p.hoff) & p.mask) : p.hoff);
+            if (tid + u * ROWS_THREADS < p.tile_elems) {
+                const int a = p.xf ? quant1(__int_as_float(pre[u]), p.qscale, p.qQ) : pre[u];
+                tl[tid + u * ROWS_THREADS] = (unsigned char)((pre_in >> u) & 1u ? ((a + p.hoff) & p.mask) : p.hoff);
+            }
         if (tid < p.gt * p.og * K) wl[tid] = ((uint32_t)((wpre + p.hoff) & p.mask) * (uint32_t)p.row_bytes) | my_toff;
     };
 
@@ -183,7 +220,8 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_grouped_tiled_kernel(const G
         nn += g_n;
     };
     if (tile >= p.ntiles) return;               // (never: the grid is at most ntiles)
-    prefetch(n, gb, chunk);
+    prefetch(n, gb, chunk);                     // in flight while the table is staged
+    stage_table(smem, p.img, p.img_bytes, tid);
     land();
     __syncthreads();                            // table and first tile staged
     for (; tile < p.ntiles; tile += gridDim.x) {
@@ -194,12 +232,105 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_grouped_tiled_kernel(const G
 
         const int row0 = chunk * p.ro;
         const int ocs = min(p.gt, groups - gb * p.gt) * p.og;               // output channels of this tile
-        int r = pix0_r, ox = pix0_x;
-        for (int pp = tid; pp < npix; pp += ROWS_THREADS) {
+        if constexpr (KW > 0) {
+            constexpr int NW = (3 * SW + KW + 3) / 4;                       // words of activations per filter row
+            constexpr uint32_t ROWM = (1u << GROUPED_TOFF_SHIFT) - 1u;
+            const int nslots = q4 ? (ocs + 3) >> 2 : ocs;
+            int sl = st0_s, r = st0_r, x4 = st0_x;
+            while (sl < nslots) {
+                if (row0 + r < p.Ho) {                                      // (the same for the lanes of a quad)
+                    const int oc_own = q4 ? sl * 4 + cl : sl;
+                    const int oc = min(oc_own, ocs - 1);                    // a lane beyond the last channel repeats it, stores nothing
+                    const bool own = oc_own < ocs;
+                    const uint32_t *wr = wl + oc * K;
+                    const unsigned char *tb = tl + (r * p.sh) * p.Wr + x4 * (4 * SW);
+                    uint32_t acc[4] = {0u, 0u, 0u, 0u};
+                    const int frows = p.cg * p.kh;
+                    for (int t = 0; t < frows; ++t) {
+                        uint32_t e[KW], sg[NW];
+#pragma unroll
+                        for (int kx = 0; kx < KW; ++kx) e[kx] = wr[t * KW + kx];
+                        const uint32_t *sp = reinterpret_cast<const uint32_t *>(tb + (e[0] >> GROUPED_TOFF_SHIFT));
+#pragma unroll
+                        for (int i = 0; i < NW; ++i) sg[i] = sp[i];
+#pragma unroll
+                        for (int kx = 0; kx < KW; ++kx)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const int idx = j * SW + kx;
+                                const uint32_t a2 = ((sg[idx >> 2] >> (8 * (idx & 3))) & 0xffu) << 1;
+                                acc[j] += lds_entry<SIGNED>(smem, (e[kx] & ROWM) + a2);
+                            }
+                    }
+                    const int co = gb * p.gt * p.og + oc, oy = row0 + r, ox = x4 * 4;
+                    int32_t *q = p.out + (((size_t)n * p.Cout + co) * p.Ho + oy) * p.Wo + ox;
+                    if (p.deq) {
+                        const float sc = p.scales ? p.scales[co] : p.scale;
+                        float y[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            y[j] = (float)(int32_t)acc[j] * sc;
+                            if (p.bias) y[j] = y[j] + p.bias[co];
+                            if (p.act == 1) y[j] = y[j] > 0.0f ? y[j] : 0.0f;
+                            else if (p.act == 2) y[j] = tanh_spec(y[j]);
+                        }
+                        if (p.out && own) {
+                            if (vec_out) {
+                                *reinterpret_cast<float4 *>(q) = make_float4(y[0], y[1], y[2], y[3]);
+                            } else {
+#pragma unroll
+                                for (int j = 0; j < 4; ++j)
+                                    if (ox + j < p.Wo) reinterpret_cast<float *>(q)[j] = y[j];
+                            }
+                        }
+                        if (q4) {
+                            uint32_t mine = 0;                              // byte j: code of pixel ox + j in this lane's channel
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) mine |= p.chain.code(y[j]) << (8 * j);
+                            // lane cl of the quad collects pixel ox + cl: byte l = the code lane l holds for that pixel
+                            const uint32_t v0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mine, 0x00, 0xf, 0xf, false);
+                            const uint32_t v1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mine, 0x55, 0xf, 0xf, false);
+                            const uint32_t v2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mine, 0xaa, 0xf, 0xf, false);
+                            const uint32_t v3 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mine, 0xff, 0xf, 0xf, false);
+                            const int s8 = cl * 8;
+                            const uint32_t word = ((v0 >> s8) & 0xffu) | (((v1 >> s8) & 0xffu) << 8) | (((v2 >> s8) & 0xffu) << 16) |
+                                                  (((v3 >> s8) & 0xffu) << 24);
+                            if (sl * 4 + 3 < ocs) {
+                                if (ox + cl < p.Wo) p.chain.put4(n, gb * p.gt * p.og + sl * 4, oy, ox + cl, word);
+                            } else if (own) {
+#pragma unroll
+                                for (int j = 0; j < 4; ++j)
+                                    if (ox + j < p.Wo) p.chain.put(n, co, oy, ox + j, y[j]);
+                            }
+                        } else if (p.chain.buf) {
+#pragma unroll
+                            for (int j = 0; j < 4; ++j)
+                                if (ox + j < p.Wo) p.chain.put(n, co, oy, ox + j, y[j]);
+                        }
+                    } else if (own && vec_out && p.shift < 0) {
+                        *reinterpret_cast<uint4 *>(q) = make_uint4(acc[0], acc[1], acc[2], acc[3]);
+                    } else if (own) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (ox + j < p.Wo) q[j] = p.shift < 0 ? (int32_t)acc[j] : (int32_t)((uint32_t)q[j] + (acc[j] << p.shift));
+                    }
+                }
+                x4 += sd_x;
+                if (x4 >= Wo4) { x4 -= Wo4; ++r; }
+                r += sd_r;
+                if (r >= p.ro) { r -= p.ro; ++sl; }
+                sl += sd_s;
+            }
+        } else {
+        const int nslots = (ocs + p.cpl - 1) / p.cpl;
+        int sl = it0_s, r = it0_r, ox = it0_x;
+        while (sl < nslots) {
             if (row0 + r < p.Ho) {
+                const int oc0 = sl * p.cpl, oc1 = min(ocs, oc0 + p.cpl);
                 const unsigned char *tb = tl + (r * p.sh) * p.Wr + ox * p.sw;
-                int32_t *q = p.out + (((size_t)n * p.Cout + (size_t)gb * p.gt * p.og) * p.Ho + row0 + r) * p.Wo + ox;
-                for (int oc = 0; oc < ocs; ++oc) {
+                int32_t *q = p.out + (((size_t)n * p.Cout + (size_t)gb * p.gt * p.og + oc0) * p.Ho + row0 + r) * p.Wo + ox;
+                uint32_t codes = 0;
+                for (int oc = oc0; oc < oc1; ++oc) {
                     const uint32_t *wr = wl + oc * K;
                     uint32_t acc = 0;
                     int k = 0;
@@ -217,13 +348,38 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_grouped_tiled_kernel(const G
                         const uint32_t e = wr[k];
                         acc += lds_entry<SIGNED>(smem, (e & ((1u << GROUPED_TOFF_SHIFT) - 1u)) + ((uint32_t)tb[e >> GROUPED_TOFF_SHIFT] << 1));
                     }
-                    if (p.shift < 0) *q = (int32_t)acc;
-                    else *q = (int32_t)((uint32_t)*q + (acc << p.shift));
+                    if (p.deq) {
+                        const int co = gb * p.gt * p.og + oc;
+                        float y = (float)(int32_t)acc * (p.scales ? p.scales[co] : p.scale);
+                        if (p.bias) y = y + p.bias[co];
+                        if (p.act == 1) y = y > 0.0f ? y : 0.0f;
+                        else if (p.act == 2) y = tanh_spec(y);
+                        if (p.out) *reinterpret_cast<float *>(q) = y;
+                        if (p.chain.buf) {
+                            if (p.chain4 && (oc | 3) < ocs) {       // four channels of this pixel make one word of the copy
+                                codes |= p.chain.code(y) << ((oc & 3) * 8);
+                                if ((oc & 3) == 3) {
+                                    p.chain.put4(n, co - 3, row0 + r, ox, codes);
+                                    codes = 0;
+                                }
+                            } else {
+                                p.chain.put(n, co, row0 + r, ox, y);
+                            }
+                        }
+                    } else if (p.shift < 0) {
+                        *q = (int32_t)acc;
+                    } else {
+                        *q = (int32_t)((uint32_t)*q + (acc << p.shift));
+                    }
                     q += (size_t)p.Ho * p.Wo;
                 }
             }
-            r += step_r; ox += step_x;
+            ox += d_x;
             if (ox >= p.Wo) { ox -= p.Wo; ++r; }
+            r += d_r;
+            if (r >= p.ro) { r -= p.ro; ++sl; }
+            sl += d_s;
+        }
         }
         __syncthreads();                        // everyone has finished reading this tile
         if (more) land();

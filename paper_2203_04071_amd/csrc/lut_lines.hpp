@@ -64,6 +64,14 @@ struct ChainOut {
         const size_t a = xmajor ? ((row * (Cp >> 2) + (c >> 2)) * Wp + ox + pw) * 4 + (c & 3) : (row * Wp + ox + pw) * Cp + c;
         buf[a] = (int8_t)q;
     }
+    // the same for channels c .. c + 3 (c a multiple of 4, Cp a multiple of 4) of one pixel: they are one aligned word
+    // of either copy
+    __device__ __forceinline__ uint32_t code(float y) const { return (uint32_t)quant1(y, scale, Q) & mask; }
+    __device__ __forceinline__ void put4(int img, int c, int oy, int ox, uint32_t codes) const {
+        const size_t row = (size_t)img * Hp + oy + ph;
+        const size_t a = xmajor ? ((row * (Cp >> 2) + (c >> 2)) * Wp + ox + pw) * 4 : (row * Wp + ox + pw) * Cp + c;
+        *reinterpret_cast<uint32_t *>(buf + a) = codes;
+    }
 };
 
 struct LinesParams {

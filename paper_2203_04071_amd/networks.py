@@ -260,10 +260,30 @@ class SeparableConv:
         self.p_pw = B.adapt_weights_pack_conv2d(self.lut, self.q_pw)
         self.stride, self.pad = cfg["stride"], cfg["pad"]
         self.scales = None
+        self._chain_shape = None
 
-    def forward(self, x):
+    def _forward_fused(self, x, keep_y):
+        """Frozen scales: the depthwise layer quantises x itself and writes the pointwise layer's input copy
+        (and y only when asked for), then the pointwise layer runs on that copy: two kernels in all."""
+        s_x, s_y = self.scales
+        n, cin, h, w = x.shape
+        kh, kw = self.q_dw.shape[2:]
+        ho, wo = B.conv_out_hw(h, w, kh, kw, self.stride, self.stride, self.pad, self.pad, 1, 1)
+        shape = (n, ho, wo)
+        if self._chain_shape != shape:
+            B.adapt_conv2d_chain_prepare(self.p_pw, n, ho, wo)
+            self._chain_shape = shape
+        y = B.adapt_conv2d_grouped_layer_f32(self.lut, x, self.q_dw, s_x, _f(s_x) * _f(self.s_dw), (self.stride, self.stride),
+                                             (self.pad, self.pad), groups=cin, want_out=keep_y, next_pw=self.p_pw, s_next=s_y)
+        out = torch.empty((n, self.q_pw.shape[0], ho, wo), dtype=torch.float32, device=x.device)
+        B.adapt_conv2d_layer_chain_f32(self.p_pw, None, s_y, _f(s_y) * _f(self.s_pw), out, in_shape=(n, ho, wo))
+        return dict(out=out, y=y, scales=[s_x, s_y])
+
+    def forward(self, x, fused=True, keep_y=False):
         bits = self.bits
         cin = x.shape[1]
+        if fused and self.scales is not None:
+            return self._forward_fused(x, keep_y)
         s_x = self.scales[0] if self.scales is not None else calibrated_scale(x, bits)
         qx = B.adapt_quantize_f32(x, s_x, bits)
         acc_dw = B.adapt_approx_conv2d(self.lut, qx, self.q_dw, (self.stride, self.stride), (self.pad, self.pad), groups=cin)

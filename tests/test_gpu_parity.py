@@ -317,7 +317,12 @@ GROUPED_CASES = [
     (2, 32, 12, 12, 64, 3, 3, 1, 1, 1, 1, 1, 1, 4),        # 4 groups of 8 -> 16: rows kernel, one launch over the groups
     (1, 48, 10, 10, 40, 3, 3, 2, 2, 1, 1, 1, 1, 2),        # 2 groups of 24 -> 20 (ragged channel tile)
     (3, 16, 33, 33, 16, 1, 1, 1, 1, 0, 0, 1, 1, 2),        # 1x1 grouped, 8 -> 8 per group
-    (1, 8, 6, 210, 4, 5, 5, 1, 1, 2, 2, 1, 1, 2),          # input region of one output row too large to stage: direct form
+    (1, 8, 6, 210, 4, 5, 5, 1, 1, 2, 2, 1, 1, 2),          # wide rows: few output rows per tile
+    (1, 8, 6, 900, 4, 5, 5, 1, 1, 2, 2, 1, 1, 2),          # input region of one output row too large to stage: direct form
+    (2, 16, 20, 20, 16, 3, 3, 2, 2, 1, 1, 1, 1, 16),       # depthwise 3x3 stride 2
+    (2, 10, 11, 9, 10, 5, 5, 1, 1, 2, 2, 1, 1, 10),        # depthwise 5x5, width not a multiple of 4
+    (1, 6, 9, 14, 6, 3, 5, 1, 2, 1, 2, 1, 1, 6),           # 3x5 filter, horizontal stride 2
+    (1, 6, 9, 14, 6, 3, 3, 1, 1, 1, 2, 1, 2, 6),           # horizontal dilation: pixel by pixel
     (2, 3, 70, 70, 3, 3, 3, 1, 1, 1, 1, 1, 1, 3),          # depthwise, planes larger than a tile: several row chunks
     (1, 64, 8, 8, 64, 3, 3, 1, 1, 1, 1, 1, 1, 64),         # small planes, many channels
 ]
@@ -358,8 +363,13 @@ def test_separable_convolution_matches_oracle(B):
     assert (host(got["acc_dw"]) == want["acc_dw"]).all()
     assert bits_equal(host(got["y"]), want["y"])
     assert bits_equal(host(got["out"]), want["out"])
-    again = net.forward(dev(cfg["x"]))
+    again = net.forward(dev(cfg["x"]), fused=False)             # frozen scales, separate steps
     assert bits_equal(host(again["out"]), want["out"])
+    for keep_y in (True, False):                                # frozen scales, two kernels
+        again = net.forward(dev(cfg["x"]), keep_y=keep_y)
+        assert bits_equal(host(again["out"]), want["out"])
+        if keep_y:
+            assert bits_equal(host(again["y"]), want["y"])
 
 
 def test_conv2d_padding_is_looked_up(B):
@@ -1081,10 +1091,12 @@ def test_separable_block_full_size_as_benchmarked(B):
     want = onet.separable_conv(cfg, threads=orc.host_threads())
     net = gnet.SeparableConv(cfg)
     net.forward(dev(cfg["x"]))                  # calibration
+    first = net.forward(dev(cfg["x"]), fused=False)
+    assert (host(first["acc_dw"]) == want["acc_dw"]).all()
     got = gnet.Captured(net, dev(cfg["x"])).replay()          # frozen scales, as a graph replay like the benchmark
     torch.cuda.synchronize()
-    assert (host(got["acc_dw"]) == want["acc_dw"]).all()
     assert_f32_close(host(got["out"]), want["out"])
+    assert bits_equal(host(got["out"]), host(first["out"]))
 
 
 def test_gru_full_size_as_benchmarked(B):
@@ -1326,6 +1338,99 @@ def test_chained_conv_layers_match_unchained_and_oracle(B, case):
                                        in_shape=(N,) + shapes[2][2:])
         for i in range(3):
             assert bits_equal(host(outs[i]), acts[i + 1]), (rep, i)
+
+
+GROUPED_LAYER_CASES = [
+    # N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, groups, Cout of the 1x1 consumer (0: none)
+    (2, 6, 5, 5, 6, 3, 3, 1, 1, 1, 1, 1, 1, 6, 0),
+    (3, 32, 16, 16, 32, 3, 3, 1, 1, 1, 1, 1, 1, 32, 64),      # separable block, wide consumer
+    (2, 24, 15, 13, 24, 5, 5, 2, 2, 2, 2, 1, 1, 24, 10),      # 5x5 stride 2, ragged; generic consumer
+    (2, 8, 9, 9, 16, 3, 3, 1, 1, 1, 1, 1, 1, 8, 12),          # channel multiplier 2
+    (1, 4, 8, 8, 8, 3, 3, 1, 1, 2, 2, 2, 2, 2, 0),            # 2 groups of 2 -> 4, dilated
+    (2, 12, 7, 7, 9, 3, 3, 1, 1, 1, 1, 1, 1, 3, 5),           # 3 groups of 4 -> 3
+    (2, 3, 70, 70, 3, 3, 3, 1, 1, 1, 1, 1, 1, 3, 4),          # planes larger than a tile: several row chunks
+    (1, 64, 8, 8, 64, 3, 3, 1, 1, 1, 1, 1, 1, 64, 32),
+    (4, 128, 32, 32, 128, 3, 3, 1, 1, 1, 1, 1, 1, 128, 128),  # the benchmarked block at a smaller batch
+    (8, 16, 32, 32, 16, 3, 3, 1, 1, 1, 1, 1, 1, 16, -32),     # 3x3 consumer with an x-major copy
+    (3, 32, 17, 19, 32, 5, 5, 2, 2, 2, 2, 1, 1, 32, -16),     # 5x5 stride 2 into a 3x3 consumer, ragged widths
+    (2, 10, 12, 12, 20, 3, 3, 1, 1, 1, 1, 1, 1, 5, 8),        # 5 groups of 2 -> 4: quads span groups
+]
+
+
+@pytest.mark.parametrize("bits", [6, 8])
+@pytest.mark.parametrize("case", GROUPED_LAYER_CASES)
+def test_grouped_conv2d_layer_f32(B, bits, case):
+    """Depthwise-style layer in one kernel: quantisation of x, the sums, rescaling / bias / activation, and the quantised
+    input copy of a following 1x1 layer, all against the oracle's separate steps."""
+    N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, g, c_next = case
+    rng = np.random.default_rng(bits + sum(case))
+    lut = wl.make_lut(bits)
+    L = B.Lut(lut, bits)
+    x = rng.standard_normal((N, Cin, H, W)).astype(np.float32)
+    w = wl.random_i8(rng, (Cout, Cin // g, kh, kw), bits, "gauss")
+    bias = rng.standard_normal(Cout).astype(np.float32)
+    s_x = orc.scale_from_amax(orc.absmax(x), bits)
+    acc = orc.approx_conv2d(lut, bits, orc.quantize(x, s_x, bits), w, (sh, sw), (ph, pw), (dh, dw), g, threads=8)
+    n_, c_, h_, w_ = acc.shape
+    s_out = np.float32(s_x) * np.float32(0.02)
+    s_vec = (np.float32(s_x) * rng.uniform(0.01, 0.03, size=Cout).astype(np.float32)).astype(np.float32)
+    for sc, b, act in ((s_out, None, 0), (s_out, bias, 1), (s_vec, bias, 2)):
+        want = (orc.dequant_per_channel if isinstance(sc, np.ndarray) else orc.dequant)(acc, sc, n_, c_, h_ * w_, b)
+        want = (orc.relu(want) if act == 1 else orc.tanh(want) if act == 2 else want).reshape(acc.shape)
+        got = B.adapt_conv2d_grouped_layer_f32(L, dev(x), dev(w), s_x, dev(sc) if isinstance(sc, np.ndarray) else sc, (sh, sw), (ph, pw),
+                                               (dh, dw), g, dev(b) if b is not None else None, act)
+        assert bits_equal(host(got), want), (b is not None, act)
+    if not c_next:
+        return
+    # chained into a 1x1 layer: with and without the fp32 output of the grouped layer
+    y = orc.relu(orc.dequant(acc, s_out, n_, c_, h_ * w_, bias)).reshape(acc.shape)
+    s_y = orc.scale_from_amax(orc.absmax(y), bits)
+    k2, c_next = (3, -c_next) if c_next < 0 else (1, c_next)      # negative: the consumer is a 3x3 layer with padding 1
+    w2 = wl.random_i8(rng, (c_next, Cout, k2, k2), bits, "gauss")
+    acc2 = orc.approx_conv2d(lut, bits, orc.quantize(y, s_y, bits), w2, (1, 1), (k2 // 2, k2 // 2), threads=8)
+    want2 = orc.dequant(acc2, np.float32(s_y) * np.float32(0.01), n_, c_next, h_ * w_).reshape(acc2.shape)
+    p2 = B.adapt_weights_pack_conv2d(L, dev(w2))
+    B.adapt_conv2d_chain_prepare(p2, N, h_, w_, (1, 1), (k2 // 2, k2 // 2))
+    out2 = torch.empty(acc2.shape, dtype=torch.float32, device="cuda")
+    for want_out in (True, False, True):
+        got = B.adapt_conv2d_grouped_layer_f32(L, dev(x), dev(w), s_x, s_out, (sh, sw), (ph, pw), (dh, dw), g, dev(bias), B.ACT_RELU,
+                                               want_out=want_out, next_pw=p2, s_next=s_y)
+        assert (got is None) == (not want_out)
+        if want_out:
+            assert bits_equal(host(got), y)
+        out2.zero_()
+        B.adapt_conv2d_layer_chain_f32(p2, None, s_y, np.float32(s_y) * np.float32(0.01), out2, (1, 1), (k2 // 2, k2 // 2),
+                                       in_shape=(N, h_, w_))
+        assert bits_equal(host(out2), want2), want_out
+
+
+def test_grouped_layer_refusals(B):
+    L = B.Lut(wl.make_lut(8), 8)
+    rng = np.random.default_rng(4)
+    x = torch.zeros((1, 8, 6, 1000), device="cuda")
+    # input region of one output row too large to stage; ordinary convolution; two-pass table: the separate calls serve these
+    with pytest.raises(B.AdaptError) as e:
+        B.adapt_conv2d_grouped_layer_f32(L, x, dev(wl.random_i8(rng, (4, 4, 5, 5), 8)), 1.0, 1.0, (1, 1), (2, 2), groups=2)
+    assert e.value.code == -2
+    with pytest.raises(B.AdaptError) as e:
+        B.adapt_conv2d_grouped_layer_f32(L, x, dev(wl.random_i8(rng, (4, 8, 3, 3), 8)), 1.0, 1.0, (1, 1), (1, 1), groups=1)
+    assert e.value.code == -2
+    wide = B.Lut(rng.integers(-2**20, 2**20, size=(64, 64)).astype(np.int32), 6)
+    with pytest.raises(B.AdaptError) as e:
+        B.adapt_conv2d_grouped_layer_f32(wide, torch.zeros((1, 8, 6, 6), device="cuda"), dev(wl.random_i8(rng, (8, 1, 3, 3), 6)), 1.0, 1.0,
+                                         (1, 1), (1, 1), groups=8)
+    assert e.value.code == -2
+    # a consumer that was not prepared, or prepared for another shape
+    p1 = B.adapt_weights_pack_conv2d(L, dev(wl.random_i8(rng, (8, 8, 1, 1), 8)))
+    xs = torch.zeros((1, 8, 6, 6), device="cuda")
+    wd = dev(wl.random_i8(rng, (8, 1, 3, 3), 8))
+    with pytest.raises(B.AdaptError) as e:
+        B.adapt_conv2d_grouped_layer_f32(L, xs, wd, 1.0, 1.0, (1, 1), (1, 1), groups=8, next_pw=p1, s_next=1.0)
+    assert e.value.code == -1
+    B.adapt_conv2d_chain_prepare(p1, 1, 5, 6)
+    with pytest.raises(B.AdaptError) as e:
+        B.adapt_conv2d_grouped_layer_f32(L, xs, wd, 1.0, 1.0, (1, 1), (1, 1), groups=8, next_pw=p1, s_next=1.0)
+    assert e.value.code == -1
 
 
 def test_chain_refuses_unprepared_handles(B):
