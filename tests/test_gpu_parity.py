@@ -1283,6 +1283,73 @@ def test_random_shapes_match_oracle(B, seed):
     assert not bad, bad
 
 
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_grouped_layers_match_oracle(B, seed):
+    """Seeded random depthwise-style layers through the one-kernel layer call (fp32 in, scalar or per-channel output
+    scale, bias, activation), half of them chained into a following 1x1 or 3x3 layer: y and the consumer's output
+    bit-identical to the oracle's separate steps."""
+    rng = np.random.default_rng(seed)
+    bad, ran = [], 0
+    for it in range(70):
+        bits = int(rng.choice([5, 6, 8]))
+        lut = wl.make_lut(bits)
+        L = B.Lut(lut, bits)
+        cg = int(rng.choice([1, 1, 1, 2, 3])); og = int(rng.choice([1, 1, 2, 3, 4])); g = int(rng.integers(2, 48))
+        Cin, Cout = cg * g, og * g
+        N = int(rng.choice([1, 2, 5])); H = int(rng.integers(3, 45)); W = int(rng.integers(3, 45))
+        kh = int(rng.choice([1, 3, 5])); kw = int(rng.choice([1, 3, 3, 5]))
+        sh = int(rng.choice([1, 1, 2])); sw = int(rng.choice([1, 1, 2])); ph = int(rng.integers(0, 3)); pw_ = int(rng.integers(0, 3))
+        dh = int(rng.choice([1, 1, 2])); dw = int(rng.choice([1, 1, 1, 2]))
+        if H + 2 * ph < dh * (kh - 1) + 1 or W + 2 * pw_ < dw * (kw - 1) + 1:
+            continue
+        act = int(rng.choice([0, 1, 2])); use_bias = rng.random() < 0.6; per_ch = rng.random() < 0.4
+        chain = rng.random() < 0.5
+        k2 = int(rng.choice([1, 3])); c2 = int(rng.choice([3, 8, 16, 64]))
+        desc = (bits, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw_, dh, dw, g, act, use_bias, per_ch, chain, k2, c2)
+        x = rng.standard_normal((N, Cin, H, W)).astype(np.float32)
+        w = wl.random_i8(rng, (Cout, cg, kh, kw), bits, "gauss")
+        bias = rng.standard_normal(Cout).astype(np.float32) if use_bias else None
+        s_x = orc.scale_from_amax(orc.absmax(x), bits)
+        acc = orc.approx_conv2d(lut, bits, orc.quantize(x, s_x, bits), w, (sh, sw), (ph, pw_), (dh, dw), g, threads=8)
+        n_, c_, h_, w_ = acc.shape
+        if per_ch:
+            sc = (np.float32(s_x) * rng.uniform(0.01, 0.03, size=Cout).astype(np.float32)).astype(np.float32)
+            y = orc.dequant_per_channel(acc, sc, n_, c_, h_ * w_, bias)
+        else:
+            sc = np.float32(s_x) * np.float32(0.02)
+            y = orc.dequant(acc, sc, n_, c_, h_ * w_, bias)
+        y = (orc.relu(y) if act == 1 else orc.tanh(y) if act == 2 else y).reshape(acc.shape)
+        try:
+            kw_args = {}
+            if chain:
+                s_y = orc.scale_from_amax(orc.absmax(y), bits)
+                if not s_y > 0:
+                    continue
+                w2 = wl.random_i8(rng, (c2, Cout, k2, k2), bits, "gauss")
+                acc2 = orc.approx_conv2d(lut, bits, orc.quantize(y, s_y, bits), w2, (1, 1), (k2 // 2, k2 // 2), threads=8)
+                want2 = orc.dequant(acc2, np.float32(s_y) * np.float32(0.01), n_, c2, h_ * w_).reshape(acc2.shape)
+                p2 = B.adapt_weights_pack_conv2d(L, dev(w2))
+                B.adapt_conv2d_chain_prepare(p2, N, h_, w_, (1, 1), (k2 // 2, k2 // 2))
+                kw_args = dict(next_pw=p2, s_next=s_y)
+            got = B.adapt_conv2d_grouped_layer_f32(L, dev(x), dev(w), s_x, dev(sc) if per_ch else sc, (sh, sw), (ph, pw_), (dh, dw), g,
+                                                   dev(bias) if use_bias else None, act, **kw_args)
+            ok = bits_equal(host(got), y)
+            if chain:
+                out2 = torch.empty(acc2.shape, dtype=torch.float32, device="cuda")
+                B.adapt_conv2d_layer_chain_f32(p2, None, s_y, np.float32(s_y) * np.float32(0.01), out2, (1, 1), (k2 // 2, k2 // 2),
+                                               in_shape=(N, h_, w_))
+                ok = ok and bits_equal(host(out2), want2)
+            ran += 1
+        except B.AdaptError as e:
+            if e.code != -2:                    # (-2: a shape the layer kernel does not take; the separate calls serve it)
+                bad.append((desc, str(e)))
+            continue
+        if not ok:
+            bad.append(desc)
+    assert not bad, bad
+    assert ran >= 50
+
+
 # ------------------------------------------------------------------ chained convolution layers
 
 CHAIN_CASES = [
