@@ -302,6 +302,17 @@ int adapt_lstm_step_f32(const adapt_weights *w_hh, const int8_t *qh_dev, const i
                         float s_h, const float *bias_dev, float *c_dev, float *h_dev, int8_t *qh_next_dev, int B, int Hs,
                         void *stream);
 
+/* One whole time step of the recurrent part of a GRU layer in one kernel:
+ *     acc_hh = table product of qh_dev [B][Hs] with the packed W_hh [3 Hs][Hs]   (adapt_approx_linear_packed)
+ *     h' = cell(acc_ih, acc_hh, h_prev);  qh_next = quantise(h', s_h)              (adapt_gru_cell_f32)
+ * with the same integers and floats as those two calls.  w_hh: handle of adapt_weights_pack_linear for W_hh (rows in
+ * gate order r, z, n).  acc_ih_dev [B][3 Hs]; b_ih_dev, b_hh_dev [3 Hs] or NULL; h_prev_dev, h_dev [B][Hs] (may be the
+ * same buffer); qh_next_dev [B][Hs], must not alias qh_dev.
+ * Covers even Hs and single-pass tables; otherwise ADAPT_ERR_UNSUPPORTED and the caller uses the two calls above. */
+int adapt_gru_step_f32(const adapt_weights *w_hh, const int8_t *qh_dev, const int32_t *acc_ih_dev, float s_ih, float s_hh,
+                       float s_h, const float *b_ih_dev, const float *b_hh_dev, const float *h_prev_dev, float *h_dev,
+                       int8_t *qh_next_dev, int B, int Hs, void *stream);
+
 /* ------------------------------------------------------------------------------------------------
  * Operands wider than 8 bits and multipliers given as functions (Sec. III-C "Framework operation": a
  * table per multiplier or, for large bitwidths, the multiplier described as a function - both a 1-1

@@ -315,10 +315,13 @@ struct Geometry {
 // prepacked: row offsets [K][prepacked_npad] made earlier by pack_row_offsets_kernel (prepacked_npad a multiple of 16),
 // or nullptr to pack `w` into a stream-ordered temporary.
 struct LstmStep {            // see adapt::RowsParams
+    int kind = 1;            // 1: LSTM, 2: GRU
     int Hs;
     const int32_t *acc_ih;
     const float *bias;
+    const float *bias_hh = nullptr;
     float *c, *h;
+    const float *h_prev = nullptr;
     int8_t *qh_next;
     float s_ih, s_hh, s_h, Qh;
 };
@@ -346,7 +349,7 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     auto wgs = [&](int nt, int mt) { return (long long)((g.M + mt - 1) / mt) * ((g.N + nt - 1) / nt) * ngroups; };
     while (MT > 64 && (MT / 2 >= g.M || (wgs(NT, MT) < cu && Ktot / (adapt::ROWS_THREADS / (MT / 2)) >= 16))) MT /= 2;
     if ((wgs(NT, MT) < cu && g.N > 8) || (ngroups > 1 && g.N <= 8)) NT = 8;
-    if (lstm) { NT = 8; MT = 64; }      // the cell epilogue sits in the split-K reduction of the 8-column variant
+    if (lstm) { NT = lstm->kind == 2 ? 6 : 8; MT = 64; }    // the cell epilogue sits in the split-K reduction: all gates of two units
     const int KS = adapt::ROWS_THREADS / MT;
     const int Npad = prepacked ? prepacked_npad : ((g.N + NT - 1) / NT) * NT;
 
@@ -375,11 +378,13 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     const bool fuse = io && io->fused(lut->storage);
     p.deq = fuse ? 1 : 0; p.act = fuse ? io->act : 0; p.scale = fuse ? io->s_out : 1.0f; p.bias = fuse ? io->bias : nullptr;
     p.scales = fuse ? io->s_out_vec : nullptr;
-    p.lstm = lstm ? 1 : 0; p.Hs = 0; p.acc_ih = nullptr; p.c = p.h = nullptr; p.qh_next = nullptr;
+    p.lstm = lstm ? lstm->kind : 0; p.Hs = 0; p.acc_ih = nullptr; p.c = p.h = nullptr; p.qh_next = nullptr;
+    p.h_prev = nullptr; p.bias_hh = nullptr;
     p.s_ih = p.s_hh = p.s_h = p.Qh = 1.0f;
     if (lstm) {
         p.Hs = lstm->Hs; p.acc_ih = lstm->acc_ih; p.bias = lstm->bias; p.c = lstm->c; p.h = lstm->h; p.qh_next = lstm->qh_next;
         p.s_ih = lstm->s_ih; p.s_hh = lstm->s_hh; p.s_h = lstm->s_h; p.Qh = lstm->Qh;
+        p.h_prev = lstm->h_prev; p.bias_hh = lstm->bias_hh;
     }
     dim3 grid((unsigned)((g.M + MT - 1) / MT), (unsigned)(Npad / NT), (unsigned)ngroups);
     size_t lds = (size_t)lut->img_bytes;
@@ -389,6 +394,7 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
         p.shift = half == 0 ? -1 : 16;
         const bool sgn = (lut->storage == 0) || half == 1;
         if (NT == 16) rc = sgn ? launch_rows_inst<16, true>(p, grid, lds, s) : launch_rows_inst<16, false>(p, grid, lds, s);
+        else if (NT == 6) rc = launch_rows_inst<6, true>(p, grid, lds, s);      // (GRU step: single-pass tables only)
         else rc = sgn ? launch_rows_inst<8, true>(p, grid, lds, s) : launch_rows_inst<8, false>(p, grid, lds, s);
     }
     if (wofs) {
@@ -1739,8 +1745,8 @@ int adapt_lstm_step_f32(const adapt_weights *h, const int8_t *qh_dev, const int3
         const size_t n = (size_t)Hs * 4 * Hs;
         uint32_t *d = nullptr;
         HIP_TRY(hipMalloc((void **)&d, n * sizeof(uint32_t)));
-        adapt::pack_row_offsets_cell_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(h->w8_dev, d, Hs, 1 << (h->bits - 1), (1 << h->bits) - 1,
-                                                                                      h->lut->rs * 2);
+        adapt::pack_row_offsets_cell_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(h->w8_dev, d, Hs, 4, 1 << (h->bits - 1),
+                                                                                      (1 << h->bits) - 1, h->lut->rs * 2);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) {
             (void)hipFree(d);
@@ -1756,6 +1762,45 @@ int adapt_lstm_step_f32(const adapt_weights *h, const int8_t *qh_dev, const int3
     ls.Hs = Hs; ls.acc_ih = acc_ih_dev; ls.bias = bias_dev; ls.c = c_dev; ls.h = h_dev; ls.qh_next = qh_next_dev;
     ls.s_ih = s_ih; ls.s_hh = s_hh; ls.s_h = s_h; ls.Qh = (float)((1 << (h->bits - 1)) - 1);
     return run_rows(h->lut, qh_dev, nullptr, nullptr, g, s, h->wofs_cell_dev, 4 * Hs, nullptr, &ls);
+}
+
+int adapt_gru_step_f32(const adapt_weights *h, const int8_t *qh_dev, const int32_t *acc_ih_dev, float s_ih, float s_hh, float s_h,
+                       const float *b_ih_dev, const float *b_hh_dev, const float *h_prev_dev, float *h_dev, int8_t *qh_next_dev, int B,
+                       int Hs, void *stream) {
+    const char *who = "adapt_gru_step_f32";
+    int rc = check_weights(h, 0, who);
+    if (rc) return rc;
+    if (B < 1 || Hs < 1) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
+    if (h->N != 3 * Hs || h->Cin != Hs) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: handle is not a packed [3 Hs][Hs] matrix", who);
+    if (!(s_h > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: s_h must be > 0", who);
+    if (!qh_dev || !acc_ih_dev || !h_prev_dev || !h_dev || !qh_next_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
+    if (qh_dev == qh_next_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: qh_next_dev must not alias qh_dev", who);
+    if (h->storage != 0 || Hs % 2 != 0 || (long long)B * 3 * Hs > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: shape outside the fused kernel (Hs even, single-pass table)", who);
+    hipStream_t s = (hipStream_t)stream;
+    if (!h->wofs_cell_dev) {        // first use: offsets with the columns in cell order, from the handle's copy of the weights
+        const size_t n = (size_t)Hs * 3 * Hs;
+        uint32_t *d = nullptr;
+        HIP_TRY(hipMalloc((void **)&d, n * sizeof(uint32_t)));
+        adapt::pack_row_offsets_cell_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(h->w8_dev, d, Hs, 3, 1 << (h->bits - 1),
+                                                                                      (1 << h->bits) - 1, h->lut->rs * 2);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) {
+            (void)hipFree(d);
+            return fail(ADAPT_ERR_HIP, "%s: pack launch: %s", who, hipGetErrorString(e));
+        }
+        h->wofs_cell_dev = d;
+    }
+    Geometry g{};
+    g.mode = adapt::MODE_GEMM; g.M = B; g.N = 3 * Hs; g.Cin = Hs; g.taps = 1; g.kw = 1;
+    g.H = 1; g.W = 1; g.Wo = 1; g.HoWo = 1; g.sh = g.sw = g.dh = g.dw = 1; g.ph = g.pw = 0;
+    g.kstride = 1; g.img_stride = Hs;
+    LstmStep ls;
+    ls.kind = 2;
+    ls.Hs = Hs; ls.acc_ih = acc_ih_dev; ls.bias = b_ih_dev; ls.bias_hh = b_hh_dev; ls.c = nullptr; ls.h = h_dev; ls.h_prev = h_prev_dev;
+    ls.qh_next = qh_next_dev;
+    ls.s_ih = s_ih; ls.s_hh = s_hh; ls.s_h = s_h; ls.Qh = (float)((1 << (h->bits - 1)) - 1);
+    return run_rows(h->lut, qh_dev, nullptr, nullptr, g, s, h->wofs_cell_dev, 3 * Hs, nullptr, &ls);
 }
 
 /* ------------------------------------------------------------------ fp32 operations between layers */

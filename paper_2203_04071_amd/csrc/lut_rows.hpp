@@ -17,6 +17,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "elementwise.hpp"
 
 namespace adapt {
@@ -51,13 +53,16 @@ struct RowsParams {
     float scale;
     const float *scales;    // one scale per output channel (then `scale` is unused), or nullptr
     const float *bias;
-    // LSTM time step (lstm != 0; linear layer with N = 4 Hs whose offsets were packed in "cell order": packed column
-    // 8 (u / 2) + 2 g + (u % 2) is gate g of hidden unit u, so the 8 columns of a workgroup are all four gates of two
-    // units): the sums are not stored; the workgroup runs the cell for its two units (the operations of
-    // lstm_cell_kernel) and writes c, h and the quantised h of the next step.
+    // Recurrent time step (lstm = 1: LSTM, G = 4 gates; lstm = 2: GRU, G = 3; linear layer with N = G Hs whose offsets
+    // were packed in "cell order": packed column 2 G (u / 2) + 2 g + (u % 2) is gate g of hidden unit u, so the 2 G
+    // columns of a workgroup are all gates of two units): the sums are not stored; the workgroup runs the cell for its
+    // two units (the operations of lstm_cell_kernel / gru_cell_kernel) and writes (c,) h and the quantised h of the
+    // next step.  LSTM: bias = b_ih + b_hh folded by the caller.  GRU: bias = b_ih, bias_hh = b_hh, h_prev read.
     int lstm, Hs;
-    const int32_t *acc_ih;      // [M][4 Hs]
+    const int32_t *acc_ih;      // [M][G Hs]
     float *c, *h;               // [M][Hs]
+    const float *h_prev;        // [M][Hs] (GRU; may be h)
+    const float *bias_hh;       // [3 Hs] or nullptr (GRU)
     int8_t *qh_next;            // [M][Hs]
     float s_ih, s_hh, s_h, Qh;
 };
@@ -91,17 +96,20 @@ __global__ void pack_row_offsets_kernel(const int8_t *__restrict__ w, uint32_t *
     wofs[idx] = v;
 }
 
-// W_hh [4 Hs][Hs] -> row offsets [Hs][4 Hs] with the columns in cell order: packed column 8 (u / 2) + 2 g + (u % 2)
-// holds gate g of hidden unit u, i.e. weight row g * Hs + u
-__global__ void pack_row_offsets_cell_kernel(const int8_t *__restrict__ w, uint32_t *__restrict__ wofs, int Hs, int hoff, int mask,
-                                             int row_bytes) {
+// W_hh [G Hs][Hs] -> row offsets with the columns in cell order: packed column 2 G (u / 2) + 2 g + (u % 2) holds gate g
+// of hidden unit u, i.e. weight row g * Hs + u.  Stored [pair of units][k][2 G]: the 2 G columns a workgroup needs are
+// contiguous over k, so its scalar loads fetch whole cache lines that it uses completely (stored [k][column] every load
+// touched a line of its own and used 24 or 32 bytes of it).
+__global__ void pack_row_offsets_cell_kernel(const int8_t *__restrict__ w, uint32_t *__restrict__ wofs, int Hs, int G, int hoff,
+                                             int mask, int row_bytes) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int N = 4 * Hs;
+    const int N = G * Hs;
     if (idx >= (size_t)Hs * N) return;
     const int k = (int)(idx / N), cp = (int)(idx % N);
-    const int u = (cp >> 3) * 2 + (cp & 1), g = (cp >> 1) & 3;
+    const int pair = cp / (2 * G), within = cp - pair * 2 * G;
+    const int u = pair * 2 + (within & 1), g = within >> 1;
     const size_t wi = ((size_t)g * Hs + u) * Hs + k;
-    wofs[idx] = (uint32_t)(((int)w[wi] + hoff) & mask) * (uint32_t)row_bytes;
+    wofs[((size_t)pair * Hs + k) * (2 * G) + within] = (uint32_t)(((int)w[wi] + hoff) & mask) * (uint32_t)row_bytes;
 }
 
 template <bool SIGNED>
@@ -165,28 +173,35 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
 #pragma unroll
             for (int d = 0; d < 8; ++d) dst[d] = (kk + 4 * d < k_end) ? xw[(kk >> 2) + d] : 0u;
         };
-        uint32_t cur[8], nxt[8];
-        if (k < k_end) fetch(nxt, k);
-        while (k < k_end) {
+        // TILED: offsets stored [column tile][k][NT] (cell order), so the loads of consecutive k are contiguous
+        auto loop = [&](auto tiled_c) {
+            constexpr bool TILED = decltype(tiled_c)::value;
+            uint32_t cur[8], nxt[8];
+            if (k < k_end) fetch(nxt, k);
+            while (k < k_end) {
 #pragma unroll
-            for (int d = 0; d < 8; ++d) cur[d] = nxt[d];
-            if (k + 32 < k_end) fetch(nxt, k + 32);
-            const int cnt = min(32, k_end - k);
+                for (int d = 0; d < 8; ++d) cur[d] = nxt[d];
+                if (k + 32 < k_end) fetch(nxt, k + 32);
+                const int cnt = min(32, k_end - k);
+                const uint32_t *wblk = wofs + ((size_t)blockIdx.y * Ktot + k) * NT;      // (TILED)
 #pragma unroll
-            for (int d = 0; d < 8; ++d) {
-                if (4 * d < cnt) {          // uniform in the wave
+                for (int d = 0; d < 8; ++d) {
+                    if (4 * d < cnt) {          // uniform in the wave
 #pragma unroll
-                    for (int bq = 0; bq < 4; ++bq) {
-                        const int a = (int)(int8_t)(cur[d] >> (8 * bq));
-                        const uint32_t a2 = (uint32_t)(((a + p.hoff) & p.mask) << 1);
-                        const uint32_t *w1 = wofs + (size_t)(k + 4 * d + bq) * p.Npad + n0;
+                        for (int bq = 0; bq < 4; ++bq) {
+                            const int a = (int)(int8_t)(cur[d] >> (8 * bq));
+                            const uint32_t a2 = (uint32_t)(((a + p.hoff) & p.mask) << 1);
+                            const uint32_t *w1 = TILED ? wblk + (4 * d + bq) * NT : wofs + (size_t)(k + 4 * d + bq) * p.Npad + n0;
 #pragma unroll
-                        for (int n = 0; n < NT; ++n) acc[n] += lds_entry<SIGNED>(smem, w1[n] + a2);
+                            for (int n = 0; n < NT; ++n) acc[n] += lds_entry<SIGNED>(smem, w1[n] + a2);
+                        }
                     }
                 }
+                k += cnt;
             }
-            k += cnt;
-        }
+        };
+        if (p.lstm) loop(std::true_type{});
+        else loop(std::false_type{});
     }
 
     while (k < k_end) {
@@ -209,7 +224,9 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
         }
         const int fill2 = (p.mode == MODE_CONVT) ? p.a_skip2 : p.a_zero2;
         const int8_t *xp = xb + (valid ? base : 0) + (size_t)c0 * p.kstride;
-        const uint32_t *wr = wofs + (size_t)k * p.Npad + n0;
+        // (cell order: offsets stored [column tile][k][NT], see pack_row_offsets_cell_kernel)
+        const size_t wstep = p.lstm ? (size_t)NT : (size_t)p.Npad;
+        const uint32_t *wr = p.lstm ? wofs + ((size_t)blockIdx.y * Ktot + k) * NT : wofs + (size_t)k * p.Npad + n0;
         int c = 0;
         for (; c + 4 <= cnt; c += 4) {
             uint32_t a2[4];
@@ -220,7 +237,7 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
             }
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
-                const uint32_t *w4 = wr + (size_t)(c + kk) * p.Npad;
+                const uint32_t *w4 = wr + (size_t)(c + kk) * wstep;
 #pragma unroll
                 for (int n = 0; n < NT; ++n) acc[n] += lds_entry<SIGNED>(smem, w4[n] + a2[kk]);
             }
@@ -228,7 +245,7 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
         for (; c < cnt; ++c) {
             const int a = xp[(size_t)c * p.kstride];
             const uint32_t a2 = valid ? (uint32_t)(((a + p.hoff) & p.mask) << 1) : (uint32_t)fill2;
-            const uint32_t *w1 = wr + (size_t)c * p.Npad;
+            const uint32_t *w1 = wr + (size_t)c * wstep;
 #pragma unroll
             for (int n = 0; n < NT; ++n) acc[n] += lds_entry<SIGNED>(smem, w1[n] + a2);
         }
@@ -256,7 +273,40 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
 #pragma unroll
     for (int n = 0; n < NT; ++n) red[((size_t)ks * NT + n) * p.MT + r_in_tile] = acc[n];
     __syncthreads();
-    if (NT == 8 && p.lstm) {
+    if (NT == 6 && p.lstm == 2) {
+        // one thread per (row, unit of the pair): the three gate sums, then the GRU cell
+        for (int o = tid; o < 2 * p.MT; o += ROWS_THREADS) {
+            const int e = o / p.MT, r = o - e * p.MT;
+            const int m2 = blockIdx.x * p.MT + r;
+            if (m2 >= p.M) continue;
+            const int u = blockIdx.y * 2 + e;
+            const size_t ci = (size_t)m2 * p.Hs + u;
+            float gi[3], gh[3];
+#pragma unroll
+            for (int g = 0; g < 3; ++g) {
+                uint32_t s = 0;
+                for (int j = 0; j < p.KS; ++j) s += red[((size_t)j * NT + g * 2 + e) * p.MT + r];
+                float uu = (float)p.acc_ih[(size_t)m2 * 3 * p.Hs + (size_t)g * p.Hs + u] * p.s_ih;
+                if (p.bias) uu = uu + p.bias[g * p.Hs + u];
+                float vv = (float)(int32_t)s * p.s_hh;
+                if (p.bias_hh) vv = vv + p.bias_hh[g * p.Hs + u];
+                gi[g] = uu;
+                gh[g] = vv;
+            }
+            const float rg = sigmoid_spec(gi[0] + gh[0]);
+            const float zg = sigmoid_spec(gi[1] + gh[1]);
+            const float rn = rg * gh[2];
+            const float ng = tanh_spec(gi[2] + rn);
+            const float omz = 1.0f - zg;
+            const float t0 = omz * ng;
+            const float t1 = zg * p.h_prev[ci];
+            const float hn = t0 + t1;
+            p.h[ci] = hn;
+            p.qh_next[ci] = (int8_t)quant1(hn, p.s_h, p.Qh);
+        }
+        return;
+    }
+    if (NT == 8 && p.lstm == 1) {
         // one thread per (row, unit of the pair): the four gate sums, then the cell
         for (int o = tid; o < 2 * p.MT; o += ROWS_THREADS) {
             const int e = o / p.MT, r = o - e * p.MT;

@@ -203,10 +203,12 @@ class LSTM:
 class Recurrent:
     """Single-layer GRU ("gru") or plain tanh recurrent layer ("rnn") (Sec. III-B "RNN Layer"): the input products of all
     time steps as one long table product, then per step the hidden-state product (pre-packed row offsets) and the cell
-    kernel, which also writes the quantised h that the next step multiplies."""
+    kernel, which also writes the quantised h that the next step multiplies; the GRU step is one fused kernel where the
+    shape allows."""
 
-    def __init__(self, cfg, kind, device="cuda"):
+    def __init__(self, cfg, kind, device="cuda", fused_step=True):
         self.kind = kind
+        self.fused_step = fused_step and kind == "gru"
         self.gates = {"gru": 3, "rnn": 1}[kind]
         self.bits = cfg["bits"]
         self.lut = B.Lut(cfg["lut"], self.bits)
@@ -238,7 +240,20 @@ class Recurrent:
         s_ih = _f(self.s_x) * _f(self.s_wih)
         s_hh = _f(s_h) * _f(self.s_whh)
         B.adapt_quantize_f32(h, s_h, bits, out=qh)
+        qh2 = torch.empty_like(qh)
         for t in range(T):
+            if self.fused_step:
+                # product, cell and the next step's quantised h in one kernel; shapes it does not cover are refused
+                # with UNSUPPORTED and take the two calls below
+                try:
+                    B.adapt_gru_step_f32(self.p_whh, qh, acc_ih[t], s_ih, s_hh, s_h, self.b_ih, self.b_hh, h, hs[t], qh2)
+                    qh, qh2 = qh2, qh
+                    h = hs[t]
+                    continue
+                except B.AdaptError as e:
+                    if e.code != -2:
+                        raise
+                    self.fused_step = False
             B.adapt_approx_linear_packed(self.p_whh, qh, out=acc_hh)
             if self.kind == "gru":
                 B.adapt_gru_cell_f32(acc_ih[t], acc_hh, s_ih, s_hh, self.b_ih, self.b_hh, h, hs[t], qh, s_h, bits)

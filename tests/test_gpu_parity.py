@@ -181,12 +181,68 @@ def test_recurrent_layers_match_oracle(B, kind, bits):
     from paper_2203_04071_amd import networks as gnet
     cfg = wl.recurrent_workload(kind, seq=12, batch=16, isz=96, hsz=72, bits=bits)
     want = onet.gru(cfg, threads=4) if kind == "gru" else onet.rnn(cfg, threads=4)
-    net = gnet.Recurrent(cfg, kind)
+    net = gnet.Recurrent(cfg, kind, fused_step=False)               # product and cell as separate calls
     got = net.forward(dev(cfg["x"]))
     assert got["s_x"] == want["s_x"]
     assert (host(got["acc_ih"]) == want["acc_ih"]).all()
     assert (host(got["acc_hh_last"]) == want["acc_hh_last"]).all()
     assert bits_equal(host(got["hs"]), want["hs"])
+    if kind == "gru":                                               # one kernel per time step
+        net = gnet.Recurrent(cfg, kind)
+        one = net.forward(dev(cfg["x"]))
+        assert net.fused_step
+        assert bits_equal(host(one["hs"]), want["hs"])
+
+
+@pytest.mark.parametrize("shape", [(1, 2), (16, 72), (70, 130), (64, 512), (5, 6)])
+@pytest.mark.parametrize("bits", [6, 8])
+def test_gru_step_matches_product_and_cell(B, shape, bits):
+    """The one-kernel GRU time step against the oracle's product followed by its cell, with and without biases, in place
+    (h = h_prev) and out of place; odd hidden sizes are refused."""
+    Bn, Hs = shape
+    rng = np.random.default_rng(Bn * 1000 + Hs + bits)
+    lut = wl.make_lut(bits)
+    L = B.Lut(lut, bits)
+    Q = (1 << (bits - 1)) - 1
+    w_hh = wl.random_i8(rng, (3 * Hs, Hs), bits, "gauss")
+    pw = B.adapt_weights_pack_linear(L, dev(w_hh))
+    h_prev = np.tanh(rng.standard_normal((Bn, Hs))).astype(np.float32)
+    s_h = np.float32(1.0) / np.float32(Q)
+    qh = orc.quantize(h_prev, s_h, bits)
+    acc_ih = rng.integers(-40000, 40000, size=(Bn, 3 * Hs)).astype(np.int32)
+    acc_hh = orc.approx_linear(lut, bits, qh, w_hh, threads=4)
+    s_ih, s_hh = np.float32(3e-5), np.float32(2e-5)
+    b1 = rng.standard_normal(3 * Hs).astype(np.float32) * np.float32(0.2)
+    b2 = rng.standard_normal(3 * Hs).astype(np.float32) * np.float32(0.2)
+    for bi, bh in ((None, None), (b1, b2), (b1, None)):
+        want = orc.gru_cell(acc_ih, acc_hh, s_ih, s_hh, bi, bh, h_prev)
+        for inplace in (False, True):
+            hp = dev(h_prev)
+            hd = hp if inplace else torch.empty((Bn, Hs), dtype=torch.float32, device="cuda")
+            qn = torch.empty((Bn, Hs), dtype=torch.int8, device="cuda")
+            B.adapt_gru_step_f32(pw, dev(qh), dev(acc_ih), s_ih, s_hh, s_h, dev(bi) if bi is not None else None,
+                                 dev(bh) if bh is not None else None, hp, hd, qn)
+            assert bits_equal(host(hd), want), (bi is not None, bh is not None, inplace)
+            assert (host(qn) == orc.quantize(want, s_h, bits)).all()
+
+
+def test_gru_step_refusals(B):
+    L = B.Lut(wl.make_lut(7), 7)
+    rng = np.random.default_rng(9)
+    pw = B.adapt_weights_pack_linear(L, dev(wl.random_i8(rng, (9, 3), 7)))
+    z = lambda *s_, dt=torch.float32: torch.zeros(s_, dtype=dt, device="cuda")
+    with pytest.raises(B.AdaptError) as e:      # odd hidden size
+        B.adapt_gru_step_f32(pw, z(2, 3, dt=torch.int8), z(2, 9, dt=torch.int32), 1.0, 1.0, 1.0, None, None, z(2, 3), z(2, 3), z(2, 3, dt=torch.int8))
+    assert e.value.code == -2
+    pw4 = B.adapt_weights_pack_linear(L, dev(wl.random_i8(rng, (16, 4), 7)))
+    with pytest.raises(B.AdaptError) as e:      # a [4 Hs][Hs] handle
+        B.adapt_gru_step_f32(pw4, z(2, 4, dt=torch.int8), z(2, 12, dt=torch.int32), 1.0, 1.0, 1.0, None, None, z(2, 4), z(2, 4), z(2, 4, dt=torch.int8))
+    assert e.value.code == -1
+    pw3 = B.adapt_weights_pack_linear(L, dev(wl.random_i8(rng, (12, 4), 7)))
+    q = z(2, 4, dt=torch.int8)
+    with pytest.raises(B.AdaptError) as e:      # aliasing operands
+        B.adapt_gru_step_f32(pw3, q, z(2, 12, dt=torch.int32), 1.0, 1.0, 1.0, None, None, z(2, 4), z(2, 4), q)
+    assert e.value.code == -1
 
 
 # ------------------------------------------------------------------ table-lookup linear layer
@@ -1106,7 +1162,9 @@ def test_gru_full_size_as_benchmarked(B):
     from paper_2203_04071_amd import networks as gnet
     cfg = wl.recurrent_workload("gru", seq=100, batch=64, isz=512, hsz=512, bits=7)
     want = onet.gru(cfg, threads=orc.host_threads(), steps=12)
-    got = gnet.Recurrent(cfg, "gru").forward(dev(cfg["x"]))
+    net = gnet.Recurrent(cfg, "gru")
+    got = net.forward(dev(cfg["x"]))
+    assert net.fused_step, "the benchmark shape must fit the fused kernel"
     assert got["s_x"] == want["s_x"]
     assert (host(got["acc_ih"][:12]) == want["acc_ih"]).all()
     assert bits_equal(host(got["hs"][:12]), want["hs"])
