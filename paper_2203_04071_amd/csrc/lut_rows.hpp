@@ -184,19 +184,25 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
                 if (k + 32 < k_end) fetch(nxt, k + 32);
                 const int cnt = min(32, k_end - k);
                 const uint32_t *wblk = wofs + ((size_t)blockIdx.y * Ktot + k) * NT;      // (TILED)
+                // a whole block of 32 runs without branches, so that the lookups of one word overlap the sums of the last
+                auto block = [&](auto full_c) {
+                    constexpr bool FULL = decltype(full_c)::value;
 #pragma unroll
-                for (int d = 0; d < 8; ++d) {
-                    if (4 * d < cnt) {          // uniform in the wave
+                    for (int d = 0; d < 8; ++d) {
+                        if (FULL || 4 * d < cnt) {          // uniform in the wave
 #pragma unroll
-                        for (int bq = 0; bq < 4; ++bq) {
-                            const int a = (int)(int8_t)(cur[d] >> (8 * bq));
-                            const uint32_t a2 = (uint32_t)(((a + p.hoff) & p.mask) << 1);
-                            const uint32_t *w1 = TILED ? wblk + (4 * d + bq) * NT : wofs + (size_t)(k + 4 * d + bq) * p.Npad + n0;
+                            for (int bq = 0; bq < 4; ++bq) {
+                                const int a = (int)(int8_t)(cur[d] >> (8 * bq));
+                                const uint32_t a2 = (uint32_t)(((a + p.hoff) & p.mask) << 1);
+                                const uint32_t *w1 = TILED ? wblk + (4 * d + bq) * NT : wofs + (size_t)(k + 4 * d + bq) * p.Npad + n0;
 #pragma unroll
-                            for (int n = 0; n < NT; ++n) acc[n] += lds_entry<SIGNED>(smem, w1[n] + a2);
+                                for (int n = 0; n < NT; ++n) acc[n] += lds_entry<SIGNED>(smem, w1[n] + a2);
+                            }
                         }
                     }
-                }
+                };
+                if (cnt == 32) block(std::true_type{});
+                else block(std::false_type{});
                 k += cnt;
             }
         };
