@@ -1728,6 +1728,24 @@ int adapt_conv_transpose2d_layer_f32(const adapt_weights *h, const float *x_dev,
 
 /* ------------------------------------------------------------------ LSTM time step in one kernel */
 
+// first use of a [G Hs][Hs] handle for time steps: row offsets with the columns in cell order (see adapt::RowsParams),
+// from the handle's copy of the weights
+static int ensure_cell_offsets(const adapt_weights *h, int Hs, int G, hipStream_t s, const char *who) {
+    if (h->wofs_cell_dev) return ADAPT_OK;
+    const size_t n = (size_t)Hs * G * Hs;
+    uint32_t *d = nullptr;
+    HIP_TRY(hipMalloc((void **)&d, n * sizeof(uint32_t)));
+    adapt::pack_row_offsets_cell_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(h->w8_dev, d, Hs, G, 1 << (h->bits - 1),
+                                                                                  (1 << h->bits) - 1, h->lut->rs * 2);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        (void)hipFree(d);
+        return fail(ADAPT_ERR_HIP, "%s: pack launch: %s", who, hipGetErrorString(e));
+    }
+    h->wofs_cell_dev = d;
+    return ADAPT_OK;
+}
+
 int adapt_lstm_step_f32(const adapt_weights *h, const int8_t *qh_dev, const int32_t *acc_ih_dev, float s_ih, float s_hh, float s_h,
                         const float *bias_dev, float *c_dev, float *h_dev, int8_t *qh_next_dev, int B, int Hs, void *stream) {
     const char *who = "adapt_lstm_step_f32";
@@ -1741,19 +1759,7 @@ int adapt_lstm_step_f32(const adapt_weights *h, const int8_t *qh_dev, const int3
     if (h->storage != 0 || Hs % 2 != 0 || (long long)B * 4 * Hs > 0x7fffffffLL)
         return fail(ADAPT_ERR_UNSUPPORTED, "%s: shape outside the fused kernel (Hs even, single-pass table)", who);
     hipStream_t s = (hipStream_t)stream;
-    if (!h->wofs_cell_dev) {        // first use: offsets with the columns in cell order, from the handle's copy of the weights
-        const size_t n = (size_t)Hs * 4 * Hs;
-        uint32_t *d = nullptr;
-        HIP_TRY(hipMalloc((void **)&d, n * sizeof(uint32_t)));
-        adapt::pack_row_offsets_cell_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(h->w8_dev, d, Hs, 4, 1 << (h->bits - 1),
-                                                                                      (1 << h->bits) - 1, h->lut->rs * 2);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) {
-            (void)hipFree(d);
-            return fail(ADAPT_ERR_HIP, "%s: pack launch: %s", who, hipGetErrorString(e));
-        }
-        h->wofs_cell_dev = d;
-    }
+    if ((rc = ensure_cell_offsets(h, Hs, 4, s, who))) return rc;
     Geometry g{};
     g.mode = adapt::MODE_GEMM; g.M = B; g.N = 4 * Hs; g.Cin = Hs; g.taps = 1; g.kw = 1;
     g.H = 1; g.W = 1; g.Wo = 1; g.HoWo = 1; g.sh = g.sw = g.dh = g.dw = 1; g.ph = g.pw = 0;
@@ -1778,19 +1784,7 @@ int adapt_gru_step_f32(const adapt_weights *h, const int8_t *qh_dev, const int32
     if (h->storage != 0 || Hs % 2 != 0 || (long long)B * 3 * Hs > 0x7fffffffLL)
         return fail(ADAPT_ERR_UNSUPPORTED, "%s: shape outside the fused kernel (Hs even, single-pass table)", who);
     hipStream_t s = (hipStream_t)stream;
-    if (!h->wofs_cell_dev) {        // first use: offsets with the columns in cell order, from the handle's copy of the weights
-        const size_t n = (size_t)Hs * 3 * Hs;
-        uint32_t *d = nullptr;
-        HIP_TRY(hipMalloc((void **)&d, n * sizeof(uint32_t)));
-        adapt::pack_row_offsets_cell_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(h->w8_dev, d, Hs, 3, 1 << (h->bits - 1),
-                                                                                      (1 << h->bits) - 1, h->lut->rs * 2);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) {
-            (void)hipFree(d);
-            return fail(ADAPT_ERR_HIP, "%s: pack launch: %s", who, hipGetErrorString(e));
-        }
-        h->wofs_cell_dev = d;
-    }
+    if ((rc = ensure_cell_offsets(h, Hs, 3, s, who))) return rc;
     Geometry g{};
     g.mode = adapt::MODE_GEMM; g.M = B; g.N = 3 * Hs; g.Cin = Hs; g.taps = 1; g.kw = 1;
     g.H = 1; g.W = 1; g.Wo = 1; g.HoWo = 1; g.sh = g.sw = g.dh = g.dw = 1; g.ph = g.pw = 0;
