@@ -300,6 +300,8 @@ def main():
         achieved = macs / (k_avg * 1e-3)
         roof = dict(bound="lds", achieved=achieved / 1e12, peak=peak / 1e12, unit="Tlookup/s", frac=achieved / peak,
                     traffic=traffic, kernel_ms_avg=k_avg, kernel_ms_min=float(kms.min()),
+                    covers="every kernel of the table-lookup call (its quantise-and-copy kernel and the product kernel); "
+                           "the product kernel alone is listed in profiles/",
                     peak_model=f"{cus} CUs x {LDS_LANES_PER_CLK_PER_CU} LDS bank-lanes/clk x {MODEL_CLOCK_GHZ} GHz; "
                                "1 lookup (2 B) per LUT-MAC")
         if args.config == 8:
