@@ -1558,6 +1558,67 @@ def test_grouped_layer_refusals(B):
     assert e.value.code == -1
 
 
+@pytest.mark.parametrize("seed", [31, 32])
+def test_random_chains_match_oracle(B, seed):
+    """Seeded random pairs of convolution layers, the first writing the second's quantised input copy in its epilogue:
+    channel counts, image sizes, filter sizes, strides, paddings and table widths nobody picked by hand, so that every
+    producer kernel (wide, paired taps, generic, split sums) meets every copy layout."""
+    rng = np.random.default_rng(seed)
+    bad, ran = [], 0
+    th = orc.host_threads()
+    for it in range(40):
+        bits = int(rng.choice([5, 6, 7, 8]))
+        lut = wl.make_lut(bits)
+        L = B.Lut(lut, bits)
+        N = int(rng.choice([1, 2, 5, 16, 33]))
+        C0 = int(rng.choice([3, 8, 16, 24, 32, 64])); C1 = int(rng.choice([4, 8, 16, 32, 40, 64])); C2 = int(rng.choice([3, 8, 16, 32, 64]))
+        H = int(rng.integers(4, 34)); W = int(rng.integers(4, 34))
+        k1 = int(rng.choice([1, 3, 3])); s1 = int(rng.choice([1, 1, 2])); p1 = int(rng.integers(0, k1 // 2 + 1))
+        k2 = int(rng.choice([1, 3, 3, 5])); s2 = int(rng.choice([1, 1, 2])); p2 = int(rng.integers(0, k2 // 2 + 2))
+        d2 = int(rng.choice([1, 1, 2]))
+        H1 = (H + 2 * p1 - k1) // s1 + 1; W1 = (W + 2 * p1 - k1) // s1 + 1
+        if H1 < 1 or W1 < 1 or H1 + 2 * p2 < d2 * (k2 - 1) + 1 or W1 + 2 * p2 < d2 * (k2 - 1) + 1:
+            continue
+        act = int(rng.choice([0, 1])); use_res = rng.random() < 0.3
+        desc = (bits, N, C0, H, W, C1, k1, s1, p1, C2, k2, s2, p2, d2, act, use_res)
+        x = rng.standard_normal((N, C0, H, W)).astype(np.float32)
+        w1 = wl.random_i8(rng, (C1, C0, k1, k1), bits, "gauss"); w2 = wl.random_i8(rng, (C2, C1, k2, k2), bits, "gauss")
+        b1 = rng.standard_normal(C1).astype(np.float32) * np.float32(0.1)
+        s_x = orc.scale_from_amax(orc.absmax(x), bits)
+        acc1 = orc.approx_conv2d(lut, bits, orc.quantize(x, s_x, bits), w1, (s1, s1), (p1, p1), threads=th)
+        y1 = orc.dequant(acc1, np.float32(s_x) * np.float32(0.02), N, C1, H1 * W1, b1)
+        res = rng.standard_normal(acc1.shape).astype(np.float32) if use_res else None
+        if use_res:
+            y1 = orc.add(y1, res)
+        y1 = (orc.relu(y1) if act == 1 else y1).reshape(acc1.shape)
+        s_y = orc.scale_from_amax(orc.absmax(y1), bits)
+        if not s_y > 0:
+            continue
+        acc2 = orc.approx_conv2d(lut, bits, orc.quantize(y1, s_y, bits), w2, (s2, s2), (p2, p2), (d2, d2), threads=th)
+        y2 = orc.dequant(acc2, np.float32(s_y) * np.float32(0.01), N, C2, acc2.shape[2] * acc2.shape[3]).reshape(acc2.shape)
+        try:
+            pa = B.adapt_weights_pack_conv2d(L, dev(w1)); pb = B.adapt_weights_pack_conv2d(L, dev(w2))
+            B.adapt_conv2d_chain_prepare(pb, N, H1, W1, (s2, s2), (p2, p2), (d2, d2))
+            o1 = torch.empty(acc1.shape, dtype=torch.float32, device="cuda")
+            o2 = torch.empty(acc2.shape, dtype=torch.float32, device="cuda")
+            ok = True
+            for rep in range(2):
+                B.adapt_conv2d_layer_chain_f32(pa, dev(x), s_x, np.float32(s_x) * np.float32(0.02), o1, (s1, s1), (p1, p1), bias=dev(b1),
+                                               act=act, residual=dev(res) if use_res else None, next_pw=pb, s_next=s_y)
+                o2.zero_()
+                B.adapt_conv2d_layer_chain_f32(pb, None, s_y, np.float32(s_y) * np.float32(0.01), o2, (s2, s2), (p2, p2), (d2, d2),
+                                               in_shape=(N, H1, W1))
+                ok = ok and bits_equal(host(o1), y1) and bits_equal(host(o2), y2)
+            ran += 1
+        except B.AdaptError as e:
+            bad.append((desc, str(e)))
+            continue
+        if not ok:
+            bad.append(desc)
+    assert not bad, bad
+    assert ran >= 25
+
+
 def test_chain_refuses_unprepared_handles(B):
     L = B.Lut(wl.make_lut(8), 8)
     rng = np.random.default_rng(3)
