@@ -34,6 +34,9 @@ MODEL_CUS = 256
 MEASURED_TRAFFIC_BYTES = {2: (18576 * 2.0 + 8192 * 1.0 + 4646 * 2.0 + 2312 * 1.0) * 1024}
 # the product kernel alone (lut_lines_wide_kernel<4> at configuration 2), same runs
 MEASURED_KERNEL_TRAFFIC_BYTES = {2: (18576 * 2.0 + 8192 * 1.0) * 1024}
+# vector instructions per lookup of that kernel: SQ_INSTS_VALU 24 264 704 wave instructions x 64 lanes per launch of
+# 1 207 959 552 lookups (profiles/lut_lines_wide_config2.md)
+WIDE_VALU_PER_LOOKUP = 24264704 * 64 / 1207959552
 
 
 def _f(x):
@@ -327,15 +330,22 @@ def main():
             covers = "the product kernel alone (lut_lines_wide_kernel); call_ms_avg adds the call's quantise-and-copy kernel"
             if args.traffic_bytes is None:
                 traffic = MEASURED_KERNEL_TRAFFIC_BYTES.get(args.config)
+            # second bound of the same kernel: it issues WIDE_VALU_PER_LOOKUP vector instructions per lookup (counters in
+            # profiles/), 64 lanes per clock per compute unit
+            alu_peak = cus * 64 * MODEL_CLOCK_GHZ * 1e9 / WIDE_VALU_PER_LOOKUP
+            extra_bound = dict(alu_peak=alu_peak / 1e12, alu_frac=macs / (float(kms.mean()) * 1e-3) / alu_peak,
+                               alu_model=f"{cus} CUs x 64 lanes/clk x {MODEL_CLOCK_GHZ} GHz / {WIDE_VALU_PER_LOOKUP:.3f} vector "
+                                         "instructions per lookup (SQ_INSTS_VALU / lookups of this kernel)")
         else:
             kms = call_ms
             covers = "every kernel of the table-lookup call"
+            extra_bound = {}
         k_avg = float(kms.mean())
         achieved = macs / (k_avg * 1e-3)
         roof = dict(bound="lds", achieved=achieved / 1e12, peak=peak / 1e12, unit="Tlookup/s", frac=achieved / peak,
                     traffic=traffic, kernel_ms_avg=k_avg, kernel_ms_min=float(kms.min()),
                     call_ms_avg=float(call_ms.mean()), call_frac=macs / (float(call_ms.mean()) * 1e-3) / peak,
-                    call_traffic=MEASURED_TRAFFIC_BYTES.get(args.config), covers=covers,
+                    call_traffic=MEASURED_TRAFFIC_BYTES.get(args.config), covers=covers, **extra_bound,
                     peak_model=f"{cus} CUs x {LDS_LANES_PER_CLK_PER_CU} LDS bank-lanes/clk x {MODEL_CLOCK_GHZ} GHz; "
                                "1 lookup (2 B) per LUT-MAC")
         if args.config == 8:
