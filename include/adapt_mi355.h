@@ -313,6 +313,14 @@ int adapt_gru_step_f32(const adapt_weights *w_hh, const int8_t *qh_dev, const in
                        float s_h, const float *b_ih_dev, const float *b_hh_dev, const float *h_prev_dev, float *h_dev,
                        int8_t *qh_next_dev, int B, int Hs, void *stream);
 
+/* One whole time step of a plain recurrent layer in one kernel: the table product of qh_dev [B][Hs] with the packed
+ * W_hh [Hs][Hs], then adapt_rnn_cell_f32 (same integers and floats as those two calls).  acc_ih_dev, h_dev [B][Hs];
+ * bias_dev [Hs] or NULL; relu != 0: max(., 0) instead of tanh; qh_next_dev [B][Hs], must not alias qh_dev.
+ * Covers even Hs and single-pass tables; otherwise ADAPT_ERR_UNSUPPORTED and the caller uses the two calls. */
+int adapt_rnn_step_f32(const adapt_weights *w_hh, const int8_t *qh_dev, const int32_t *acc_ih_dev, float s_ih, float s_hh,
+                       float s_h, const float *bias_dev, int relu, float *h_dev, int8_t *qh_next_dev, int B, int Hs,
+                       void *stream);
+
 /* ------------------------------------------------------------------------------------------------
  * Operands wider than 8 bits and multipliers given as functions (Sec. III-C "Framework operation": a
  * table per multiplier or, for large bitwidths, the multiplier described as a function - both a 1-1

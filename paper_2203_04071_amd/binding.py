@@ -32,7 +32,7 @@ EXPORTS = [
     "adapt_linear_layer_f32", "adapt_conv2d_layer_f32", "adapt_conv_transpose2d_layer_f32",
     "adapt_conv2d_chain_prepare", "adapt_conv2d_layer_chain_f32", "adapt_conv2d_grouped_layer_f32",
     "adapt_relu_f32", "adapt_add_f32", "adapt_avgpool_hw_f32", "adapt_shortcut_a_f32",
-    "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32", "adapt_lstm_cell_q_f32", "adapt_lstm_step_f32", "adapt_gru_step_f32", "adapt_gru_cell_f32", "adapt_rnn_cell_f32",
+    "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32", "adapt_lstm_cell_q_f32", "adapt_lstm_step_f32", "adapt_gru_step_f32", "adapt_rnn_step_f32", "adapt_gru_cell_f32", "adapt_rnn_cell_f32",
     "adapt_lut16_create", "adapt_lut16_create_from_func", "adapt_lut16_destroy", "adapt_lut16_bits", "adapt_quantize_i16_f32",
     "adapt_approx_linear_i16", "adapt_approx_conv2d_i16", "adapt_approx_linear_func_i16", "adapt_approx_conv2d_func_i16",
 ]
@@ -107,6 +107,7 @@ def load() -> ctypes.CDLL:
     L.adapt_lstm_cell_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, i32, i32, vp]
     L.adapt_lstm_step_f32.argtypes = [vp, vp, vp, f32, f32, f32, vp, vp, vp, vp, i32, i32, vp]
     L.adapt_gru_step_f32.argtypes = [vp, vp, vp, f32, f32, f32, vp, vp, vp, vp, vp, i32, i32, vp]
+    L.adapt_rnn_step_f32.argtypes = [vp, vp, vp, f32, f32, f32, vp, i32, vp, vp, i32, i32, vp]
     L.adapt_lstm_cell_q_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, vp, f32, i32, i32, i32, vp]
     L.adapt_gru_cell_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, vp, vp, f32, i32, i32, i32, vp]
     L.adapt_rnn_cell_f32.argtypes = [vp, vp, f32, f32, vp, i32, vp, vp, f32, i32, i32, i32, vp]
@@ -614,6 +615,15 @@ def adapt_gru_step_f32(pw_hh: PackedWeights, qh, acc_ih, s_ih, s_hh, s_h, b_ih, 
     _chk(load().adapt_gru_step_f32(pw_hh.handle, _ptr(qh, torch.int8), _ptr(acc_ih, torch.int32), float(s_ih), float(s_hh),
                                    float(s_h), _ptr(b_ih, torch.float32), _ptr(b_hh, torch.float32), _ptr(h_prev, torch.float32),
                                    _ptr(h, torch.float32), _ptr(qh_next, torch.int8), B, Hs, _stream(stream)))
+    return h, qh_next
+
+
+def adapt_rnn_step_f32(pw_hh: PackedWeights, qh, acc_ih, s_ih, s_hh, s_h, bias, h, qh_next, relu=False, stream=None):
+    """Raises AdaptError with code -2 (UNSUPPORTED) when the shape does not fit the fused kernel."""
+    B, Hs = acc_ih.shape
+    _chk(load().adapt_rnn_step_f32(pw_hh.handle, _ptr(qh, torch.int8), _ptr(acc_ih, torch.int32), float(s_ih), float(s_hh),
+                                   float(s_h), _ptr(bias, torch.float32), 1 if relu else 0, _ptr(h, torch.float32),
+                                   _ptr(qh_next, torch.int8), B, Hs, _stream(stream)))
     return h, qh_next
 
 

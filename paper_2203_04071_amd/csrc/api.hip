@@ -315,7 +315,8 @@ struct Geometry {
 // prepacked: row offsets [K][prepacked_npad] made earlier by pack_row_offsets_kernel (prepacked_npad a multiple of 16),
 // or nullptr to pack `w` into a stream-ordered temporary.
 struct LstmStep {            // see adapt::RowsParams
-    int kind = 1;            // 1: LSTM, 2: GRU
+    int kind = 1;            // 1: LSTM, 2: GRU, 3: plain cell
+    int relu = 0;            // plain cell: ReLU instead of tanh
     int Hs;
     const int32_t *acc_ih;
     const float *bias;
@@ -349,7 +350,7 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     auto wgs = [&](int nt, int mt) { return (long long)((g.M + mt - 1) / mt) * ((g.N + nt - 1) / nt) * ngroups; };
     while (MT > 64 && (MT / 2 >= g.M || (wgs(NT, MT) < cu && Ktot / (adapt::ROWS_THREADS / (MT / 2)) >= 16))) MT /= 2;
     if ((wgs(NT, MT) < cu && g.N > 8) || (ngroups > 1 && g.N <= 8)) NT = 8;
-    if (lstm) { NT = lstm->kind == 2 ? 6 : 8; MT = 64; }    // the cell epilogue sits in the split-K reduction: all gates of two units
+    if (lstm) { NT = lstm->kind == 2 ? 6 : (lstm->kind == 3 ? 2 : 8); MT = 64; }    // the cell epilogue sits in the split-K reduction: all gates of two units
     const int KS = adapt::ROWS_THREADS / MT;
     const int Npad = prepacked ? prepacked_npad : ((g.N + NT - 1) / NT) * NT;
 
@@ -385,6 +386,7 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
         p.Hs = lstm->Hs; p.acc_ih = lstm->acc_ih; p.bias = lstm->bias; p.c = lstm->c; p.h = lstm->h; p.qh_next = lstm->qh_next;
         p.s_ih = lstm->s_ih; p.s_hh = lstm->s_hh; p.s_h = lstm->s_h; p.Qh = lstm->Qh;
         p.h_prev = lstm->h_prev; p.bias_hh = lstm->bias_hh;
+        if (lstm->kind == 3) p.act = lstm->relu ? 1 : 0;
     }
     dim3 grid((unsigned)((g.M + MT - 1) / MT), (unsigned)(Npad / NT), (unsigned)ngroups);
     size_t lds = (size_t)lut->img_bytes;
@@ -395,6 +397,7 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
         const bool sgn = (lut->storage == 0) || half == 1;
         if (NT == 16) rc = sgn ? launch_rows_inst<16, true>(p, grid, lds, s) : launch_rows_inst<16, false>(p, grid, lds, s);
         else if (NT == 6) rc = launch_rows_inst<6, true>(p, grid, lds, s);      // (GRU step: single-pass tables only)
+        else if (NT == 2) rc = launch_rows_inst<2, true>(p, grid, lds, s);      // (plain recurrent step, likewise)
         else rc = sgn ? launch_rows_inst<8, true>(p, grid, lds, s) : launch_rows_inst<8, false>(p, grid, lds, s);
     }
     if (wofs) {
@@ -1795,6 +1798,31 @@ int adapt_gru_step_f32(const adapt_weights *h, const int8_t *qh_dev, const int32
     ls.qh_next = qh_next_dev;
     ls.s_ih = s_ih; ls.s_hh = s_hh; ls.s_h = s_h; ls.Qh = (float)((1 << (h->bits - 1)) - 1);
     return run_rows(h->lut, qh_dev, nullptr, nullptr, g, s, h->wofs_cell_dev, 3 * Hs, nullptr, &ls);
+}
+
+int adapt_rnn_step_f32(const adapt_weights *h, const int8_t *qh_dev, const int32_t *acc_ih_dev, float s_ih, float s_hh, float s_h,
+                       const float *bias_dev, int relu, float *h_dev, int8_t *qh_next_dev, int B, int Hs, void *stream) {
+    const char *who = "adapt_rnn_step_f32";
+    int rc = check_weights(h, 0, who);
+    if (rc) return rc;
+    if (B < 1 || Hs < 1) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
+    if (h->N != Hs || h->Cin != Hs) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: handle is not a packed [Hs][Hs] matrix", who);
+    if (!(s_h > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: s_h must be > 0", who);
+    if (!qh_dev || !acc_ih_dev || !h_dev || !qh_next_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
+    if (qh_dev == qh_next_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: qh_next_dev must not alias qh_dev", who);
+    if (h->storage != 0 || Hs % 2 != 0 || (long long)B * Hs > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: shape outside the fused kernel (Hs even, single-pass table)", who);
+    hipStream_t s = (hipStream_t)stream;
+    if ((rc = ensure_cell_offsets(h, Hs, 1, s, who))) return rc;
+    Geometry g{};
+    g.mode = adapt::MODE_GEMM; g.M = B; g.N = Hs; g.Cin = Hs; g.taps = 1; g.kw = 1;
+    g.H = 1; g.W = 1; g.Wo = 1; g.HoWo = 1; g.sh = g.sw = g.dh = g.dw = 1; g.ph = g.pw = 0;
+    g.kstride = 1; g.img_stride = Hs;
+    LstmStep ls;
+    ls.kind = 3; ls.relu = relu ? 1 : 0;
+    ls.Hs = Hs; ls.acc_ih = acc_ih_dev; ls.bias = bias_dev; ls.c = nullptr; ls.h = h_dev; ls.qh_next = qh_next_dev;
+    ls.s_ih = s_ih; ls.s_hh = s_hh; ls.s_h = s_h; ls.Qh = (float)((1 << (h->bits - 1)) - 1);
+    return run_rows(h->lut, qh_dev, nullptr, nullptr, g, s, h->wofs_cell_dev, Hs, nullptr, &ls);
 }
 
 /* ------------------------------------------------------------------ fp32 operations between layers */

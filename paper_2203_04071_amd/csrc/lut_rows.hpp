@@ -53,7 +53,8 @@ struct RowsParams {
     float scale;
     const float *scales;    // one scale per output channel (then `scale` is unused), or nullptr
     const float *bias;
-    // Recurrent time step (lstm = 1: LSTM, G = 4 gates; lstm = 2: GRU, G = 3; linear layer with N = G Hs whose offsets
+    // Recurrent time step (lstm = 1: LSTM, G = 4 gates; lstm = 2: GRU, G = 3; lstm = 3: plain cell, G = 1, `act` = 1 for
+    // ReLU instead of tanh; linear layer with N = G Hs whose offsets
     // were packed in "cell order": packed column 2 G (u / 2) + 2 g + (u % 2) is gate g of hidden unit u, so the 2 G
     // columns of a workgroup are all gates of two units): the sums are not stored; the workgroup runs the cell for its
     // two units (the operations of lstm_cell_kernel / gru_cell_kernel) and writes (c,) h and the quantised h of the
@@ -279,6 +280,26 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
 #pragma unroll
     for (int n = 0; n < NT; ++n) red[((size_t)ks * NT + n) * p.MT + r_in_tile] = acc[n];
     __syncthreads();
+    if (NT == 2 && p.lstm == 3) {
+        // one thread per (row, unit of the pair): the sum, then the plain recurrent cell (the operations of rnn_cell_kernel)
+        for (int o = tid; o < 2 * p.MT; o += ROWS_THREADS) {
+            const int e = o / p.MT, r = o - e * p.MT;
+            const int m2 = blockIdx.x * p.MT + r;
+            if (m2 >= p.M) continue;
+            const int u = blockIdx.y * 2 + e;
+            const size_t ci = (size_t)m2 * p.Hs + u;
+            uint32_t s = 0;
+            for (int j = 0; j < p.KS; ++j) s += red[((size_t)j * NT + e) * p.MT + r];
+            const float uu = (float)p.acc_ih[ci] * p.s_ih;
+            const float vv = (float)(int32_t)s * p.s_hh;
+            float t = uu + vv;
+            t = t + (p.bias ? p.bias[u] : 0.0f);
+            const float hn = p.act == 1 ? (t > 0.0f ? t : 0.0f) : tanh_spec(t);
+            p.h[ci] = hn;
+            p.qh_next[ci] = (int8_t)quant1(hn, p.s_h, p.Qh);
+        }
+        return;
+    }
     if (NT == 6 && p.lstm == 2) {
         // one thread per (row, unit of the pair): the three gate sums, then the GRU cell
         for (int o = tid; o < 2 * p.MT; o += ROWS_THREADS) {

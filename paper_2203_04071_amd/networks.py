@@ -203,12 +203,12 @@ class LSTM:
 class Recurrent:
     """Single-layer GRU ("gru") or plain tanh recurrent layer ("rnn") (Sec. III-B "RNN Layer"): the input products of all
     time steps as one long table product, then per step the hidden-state product (pre-packed row offsets) and the cell
-    kernel, which also writes the quantised h that the next step multiplies; the GRU step is one fused kernel where the
-    shape allows."""
+    kernel, which also writes the quantised h that the next step multiplies; where the shape allows the step is one
+    fused kernel."""
 
     def __init__(self, cfg, kind, device="cuda", fused_step=True):
         self.kind = kind
-        self.fused_step = fused_step and kind == "gru"
+        self.fused_step = fused_step
         self.gates = {"gru": 3, "rnn": 1}[kind]
         self.bits = cfg["bits"]
         self.lut = B.Lut(cfg["lut"], self.bits)
@@ -246,7 +246,10 @@ class Recurrent:
                 # product, cell and the next step's quantised h in one kernel; shapes it does not cover are refused
                 # with UNSUPPORTED and take the two calls below
                 try:
-                    B.adapt_gru_step_f32(self.p_whh, qh, acc_ih[t], s_ih, s_hh, s_h, self.b_ih, self.b_hh, h, hs[t], qh2)
+                    if self.kind == "gru":
+                        B.adapt_gru_step_f32(self.p_whh, qh, acc_ih[t], s_ih, s_hh, s_h, self.b_ih, self.b_hh, h, hs[t], qh2)
+                    else:
+                        B.adapt_rnn_step_f32(self.p_whh, qh, acc_ih[t], s_ih, s_hh, s_h, self.bias, hs[t], qh2)
                     qh, qh2 = qh2, qh
                     h = hs[t]
                     continue

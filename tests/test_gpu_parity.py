@@ -187,7 +187,7 @@ def test_recurrent_layers_match_oracle(B, kind, bits):
     assert (host(got["acc_ih"]) == want["acc_ih"]).all()
     assert (host(got["acc_hh_last"]) == want["acc_hh_last"]).all()
     assert bits_equal(host(got["hs"]), want["hs"])
-    if kind == "gru":                                               # one kernel per time step
+    if True:                                                        # one kernel per time step
         net = gnet.Recurrent(cfg, kind)
         one = net.forward(dev(cfg["x"]))
         assert net.fused_step
@@ -224,6 +224,39 @@ def test_gru_step_matches_product_and_cell(B, shape, bits):
                                  dev(bh) if bh is not None else None, hp, hd, qn)
             assert bits_equal(host(hd), want), (bi is not None, bh is not None, inplace)
             assert (host(qn) == orc.quantize(want, s_h, bits)).all()
+
+
+@pytest.mark.parametrize("shape", [(1, 2), (16, 72), (70, 130), (64, 512)])
+def test_rnn_step_matches_product_and_cell(B, shape):
+    """The one-kernel plain recurrent step against the oracle's product followed by its cell (tanh and ReLU)."""
+    Bn, Hs = shape
+    bits = 7
+    rng = np.random.default_rng(Bn * 1000 + Hs)
+    lut = wl.make_lut(bits)
+    L = B.Lut(lut, bits)
+    Q = (1 << (bits - 1)) - 1
+    w_hh = wl.random_i8(rng, (Hs, Hs), bits, "gauss")
+    pw = B.adapt_weights_pack_linear(L, dev(w_hh))
+    h_prev = np.tanh(rng.standard_normal((Bn, Hs))).astype(np.float32)
+    s_h = np.float32(1.0) / np.float32(Q)
+    qh = orc.quantize(h_prev, s_h, bits)
+    acc_ih = rng.integers(-40000, 40000, size=(Bn, Hs)).astype(np.int32)
+    acc_hh = orc.approx_linear(lut, bits, qh, w_hh, threads=4)
+    s_ih, s_hh = np.float32(3e-5), np.float32(2e-5)
+    b = rng.standard_normal(Hs).astype(np.float32) * np.float32(0.2)
+    for bias, relu in ((None, False), (b, False), (b, True)):
+        want = orc.rnn_cell(acc_ih, acc_hh, s_ih, s_hh, bias, relu=relu)
+        hd = torch.empty((Bn, Hs), dtype=torch.float32, device="cuda")
+        qn = torch.empty((Bn, Hs), dtype=torch.int8, device="cuda")
+        B.adapt_rnn_step_f32(pw, dev(qh), dev(acc_ih), s_ih, s_hh, s_h, dev(bias) if bias is not None else None, hd, qn, relu=relu)
+        assert bits_equal(host(hd), want), (bias is not None, relu)
+        assert (host(qn) == orc.quantize(want, s_h, bits)).all()
+    if Hs == 2:
+        pw3 = B.adapt_weights_pack_linear(L, dev(wl.random_i8(rng, (3, 3), bits)))
+        z = lambda *s_, dt=torch.float32: torch.zeros(s_, dtype=dt, device="cuda")
+        with pytest.raises(B.AdaptError) as e:      # odd hidden size
+            B.adapt_rnn_step_f32(pw3, z(2, 3, dt=torch.int8), z(2, 3, dt=torch.int32), 1.0, 1.0, 1.0, None, z(2, 3), z(2, 3, dt=torch.int8))
+        assert e.value.code == -2
 
 
 def test_gru_step_refusals(B):
