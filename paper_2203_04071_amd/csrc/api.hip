@@ -149,6 +149,9 @@ struct adapt_weights {
     // The same derived tables in the wide order (lut_wide.hpp), made on first use by a call whose geometry takes the
     // wide-line kernel (single-pass tables, 32 | padded channels); from the handle's copy of the weights.
     mutable uint4 *dtw_dev;
+    // their entries are stored as int8 digits of (entry - dtw_c) when the table's range allows (adapt::wide_entry): the
+    // matrix-pipe instantiations of the wide kernel then do the widening additions
+    mutable int dtw_digits, dtw_c;
     // linear [4 Hs][Hs] handles used for LSTM time steps: row offsets with the columns in cell order (see
     // adapt::RowsParams), made on first use
     mutable uint32_t *wofs_cell_dev;
@@ -571,7 +574,17 @@ int launch_lines_xmajor(const adapt::LinesParams &p, unsigned grid, hipStream_t 
 
 // wide-line kernel: 8 rows per lane from an x-major copy, signed single-pass tables
 // (extra: the instantiation whose epilogue also takes the border terms of a transposed convolution off and knows tanh)
-int launch_lines_wide(const adapt::LinesParams &p, unsigned grid, bool extra, hipStream_t s) {
+template <bool EXTRA>
+int launch_lines_wide_mf(const adapt::LinesParams &p, unsigned grid, hipStream_t s) {
+    if (p.bits == 8) adapt::lut_lines_wide_kernel<4, EXTRA, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    else if (p.bits == 7) adapt::lut_lines_wide_kernel<2, EXTRA, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    else adapt::lut_lines_wide_kernel<1, EXTRA, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+int launch_lines_wide(const adapt::LinesParams &p, unsigned grid, bool extra, bool digits, hipStream_t s) {
+    if (digits) return extra ? launch_lines_wide_mf<true>(p, grid, s) : launch_lines_wide_mf<false>(p, grid, s);
     if (extra) {
         if (p.bits == 8) adapt::lut_lines_wide_kernel<4, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
         else if (p.bits == 7) adapt::lut_lines_wide_kernel<2, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
@@ -645,6 +658,7 @@ struct LinesCall {       // per-call geometry of the activation side
     // Derived tables in the wide order (lut_wide.hpp) for the x-major case, or nullptr.  Callers only provide it for
     // single-pass tables without tap pairing.
     const uint4 *dt_wide = nullptr;
+    int wide_digits = 0, wide_c = 0;    // digit form of those tables and its offset (adapt::wide_entry)
     int32_t *partial = nullptr;         // room for the partial sums when the plan splits the inner dimension
     // transposed convolution: zero sums and geometry for taking the border terms off inside the kernel (see
     // adapt::LinesParams::zsum); run_lines reports through border_done whether it did
@@ -726,6 +740,8 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     p.out_plane = c.out_plane; p.out_sy = c.out_sy; p.out_sx = c.out_sx;
     p.m_tiles = (c.M + 128 * R - 1) / (128 * R);
     p.ksplit = pl.ksplit; p.gps = pl.gps; p.ks_out_stride = split ? (long long)c.out_elems : 0;
+    // digit tables: every real lookup of an output lacks the offset (sums wrap in 32 bits like everything else)
+    p.corr = c.wide_digits ? (int)(uint32_t)((unsigned long long)((long long)q.kh * q.kw * q.Cin * (long long)c.wide_c)) : 0;
     // one base offset per lane is enough when the R rows of a lane are equally spaced in xt
     const bool regular = (c.M % R == 0) && (c.HoWo == 1 || c.Wo % R == 0);
     const bool xmajor = c.xmajor && R == 8 && c.M % 8 == 0 && c.Wo % 4 == 0;
@@ -766,7 +782,7 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
             if (grid > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "lines path: grid too large");
             if (use_wide) {
                 p.dt = c.dt_wide;
-                rc = launch_lines_wide(p, (unsigned)grid, extra, s);
+                rc = launch_lines_wide(p, (unsigned)grid, extra, c.wide_digits != 0, s);
             } else if (xmajor) rc = sgn ? launch_lines_xmajor<true>(p, (unsigned)grid, s) : launch_lines_xmajor<false>(p, (unsigned)grid, s);
             else if (R == 8) rc = launch_lines_r<8>(p, (unsigned)grid, sgn, regular, s);
             else if (R == 4) rc = launch_lines_r<4>(p, (unsigned)grid, sgn, regular, s);
@@ -799,17 +815,22 @@ const uint4 *ensure_wide(const adapt_weights *h, hipStream_t s) {
     const size_t total = h->dt_bytes / 16;
     size_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
+    // digit form when every entry minus an offset fits two int8 digits to base -128
+    const long long span = (long long)h->lut->max_entry - (long long)h->lut->min_entry;
+    const int digits = (span <= 32895 && !getenv("ADAPT_WIDE_PLAIN")) ? 1 : 0;
+    const int digit_c = digits ? h->lut->min_entry + 16384 : 0;
     if (h->kind == 2)
         adapt::pack_wide_tables_convt_kernel<<<(unsigned)blocks, 256, 0, s>>>(h->lut->lut16_dev[0], h->w8_dev, d, h->bits, h->N, h->Cin, h->kh,
-                                                                             h->kw, h->stride, h->Cp, h->n_tiles);
+                                                                             h->kw, h->stride, h->Cp, h->n_tiles, digits, digit_c);
     else
         adapt::pack_wide_tables_kernel<<<(unsigned)blocks, 256, 0, s>>>(h->lut->lut16_dev[0], h->w8_dev, d, h->bits, h->N, h->Cin,
-                                                                       h->kh * h->kw, h->Cp, h->n_tiles, 0);
+                                                                       h->kh * h->kw, h->Cp, h->n_tiles, 0, digits, digit_c);
     if (hipGetLastError() != hipSuccess) {
         (void)hipFree(d);
         return nullptr;
     }
     h->dtw_dev = d;
+    h->dtw_digits = digits; h->dtw_c = digit_c;
     return d;
 }
 
@@ -862,6 +883,7 @@ int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
         c.xmajor = 1; c.ch_stride = M;
         c.out_plane = 1; c.out_sy = 0; c.out_sx = q.N;
         c.dt_wide = ensure_wide(wh, s);
+        if (c.dt_wide) { c.wide_digits = wh->dtw_digits; c.wide_c = wh->dtw_c; }
     } else {
         if (Kp != K || from_f32 || part_bytes) {
             int wrc = ws_get(ws, copy_bytes + part_bytes, s, (void **)&tmp);
@@ -932,6 +954,7 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     c.out_elems = out_elems; c.out_channels = (size_t)q.N; c.out_inner = (size_t)Ho * Wo;
     if (part_bytes) c.partial = reinterpret_cast<int32_t *>(xt + copy_bytes);
     if (xmajor) c.dt_wide = ensure_wide(wh, s);
+    if (c.dt_wide) { c.wide_digits = wh->dtw_digits; c.wide_c = wh->dtw_c; }
     bool finished = false;
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io, true, nullptr, &finished);
     rc = ws_put(ws, xt, s, rc);
@@ -995,6 +1018,7 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
     c.out_elems = out_elems; c.out_channels = (size_t)q.N; c.out_inner = (size_t)Ho * Wo;
     if (part_bytes) c.partial = reinterpret_cast<int32_t *>(xt + copy_bytes);
     if (xmajor) c.dt_wide = ensure_wide(wh, s);
+    if (c.dt_wide) { c.wide_digits = wh->dtw_digits; c.wide_c = wh->dtw_c; }
     if (border && out_elems < 0x7fffffffull) {      // let the product kernel take the border terms off where it can
         c.zsum = zsum;
         c.cv_Ho = Ho; c.cv_Wo = Wo; c.cv_H = H; c.cv_W = W; c.cv_kh = kh; c.cv_kw = kw; c.cv_s = st; c.cv_pad = pad; c.cv_Ly = Ly; c.cv_Lx = Lx;
@@ -1234,7 +1258,7 @@ static int weights_pack(adapt_weights **out, const adapt_lut *lut, const int8_t 
     h->dt_bytes = q.dt_bytes;
     h->dt_dev[0] = h->dt_dev[1] = nullptr;
     h->stride = 1; h->phased = false; h->zsum_dev = nullptr; h->w8_dev = nullptr; h->lut = lut;
-    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0; h->dtw_dev = nullptr; h->wofs_cell_dev = nullptr;
+    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0; h->dtw_dev = nullptr; h->dtw_digits = 0; h->dtw_c = 0; h->wofs_cell_dev = nullptr;
     {   // copy of the weights (for table orders made later)
         const size_t wbytes = (size_t)N * Cin * kh * kw;
         hipError_t e = hipMalloc((void **)&h->w8_dev, wbytes);
@@ -1316,7 +1340,7 @@ int adapt_weights_pack_conv_transpose2d(adapt_weights **out, const adapt_lut *lu
     h->Cp = h->Cc = h->n_tiles = 0; h->dt_bytes = 0; h->pair_g = 0;
     h->dt_dev[0] = h->dt_dev[1] = nullptr;
     h->zsum_dev = nullptr; h->w8_dev = nullptr; h->lut = lut;
-    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0; h->dtw_dev = nullptr; h->wofs_cell_dev = nullptr;
+    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0; h->dtw_dev = nullptr; h->dtw_digits = 0; h->dtw_c = 0; h->wofs_cell_dev = nullptr;
     h->phased = kh % stride == 0 && kw % stride == 0 && stride <= 8;
     const size_t wbytes = (size_t)Cout * Cin * kh * kw;
     hipError_t e = hipMalloc((void **)&h->w8_dev, wbytes);

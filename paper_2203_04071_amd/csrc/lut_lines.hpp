@@ -110,6 +110,7 @@ struct LinesParams {
     // reduce_partials_kernel adds the slices up.  ksplit == 1: no split.
     int ksplit, gps;
     long long ks_out_stride;
+    int corr;               // wide kernel with digit tables: added to every finished sum (see lut_wide.hpp); else 0
     // Tap pairing (fast kernel, PAIRED): layers with fewer than 32 (padded) channels per tap put pair_g = 32 / Cp taps
     // side by side in a group of four steps: k-sub j serves tap pair_g * group + j / pair_cg and the four channels
     // 4 * (j % pair_cg) + step of it (pair_cg = Cp / 4).  `taps` then counts groups and Cc is 4; taps_real is the

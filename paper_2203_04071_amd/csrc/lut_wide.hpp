@@ -30,9 +30,23 @@ constexpr int WIDE_BUF_BYTES = 65536;
 // Derived tables in the wide order: [n_tile][wide step = 2 * group + h][line a][slot t] x 16 bytes, slot t of step h of
 // a group holding inner index 32 * group + 4 * (t / 2) + 2 * h + (t % 2)  (group counts 32-index blocks over all taps:
 // tap = group / (Cp / 32)).  wmode as in pack_line_tables_kernel.
+// digit form (digits != 0): an entry e is stored as the two int8 digits of e - digit_c = d0 - 128 d1 (low byte d0, high
+// byte d1; |e - digit_c| stays within [-16384, 16511], which the caller has checked), so that an int8 matrix
+// instruction with the weights (1, -128) rebuilds it; padded channels hold the digits of 0 and the kernel adds
+// digit_c times the number of real lookups at the end.
+__device__ __forceinline__ uint32_t wide_entry(uint32_t v16, int digits, int digit_c) {
+    if (!digits) return v16;
+    const int e = (int)(int16_t)v16 - digit_c;
+    int t = 127 - e;                                    // d1 = floor((127 - e) / 128), at most 127
+    int d1 = t >= 0 ? t >> 7 : -((-t + 127) >> 7);
+    if (d1 > 127) d1 = 127;
+    const int d0 = e + 128 * d1;
+    return (uint32_t)(d0 & 0xff) | ((uint32_t)(d1 & 0xff) << 8);
+}
+
 __global__ void pack_wide_tables_kernel(const uint16_t *__restrict__ lut16, const int8_t *__restrict__ w,
                                         uint4 *__restrict__ dt, int bits, int N, int Cin, int taps, int Cp, int n_tiles,
-                                        int wmode) {
+                                        int wmode, int digits, int digit_c) {
     const int lines = 1 << bits, mask = lines - 1;
     const size_t per_table = (size_t)lines * 16;
     const int gpt = Cp / 32;                        // groups per tap
@@ -55,7 +69,7 @@ __global__ void pack_wide_tables_kernel(const uint16_t *__restrict__ lut16, cons
             uint32_t v = 0;
             if (n < N && ci < Cin) {
                 const size_t wi = wmode == 0 ? ((size_t)n * Cin + ci) * taps + tap : ((size_t)ci * N + n) * taps + tap;
-                v = lut16[(size_t)a * lines + ((int)w[wi] & mask)];
+                v = wide_entry(lut16[(size_t)a * lines + ((int)w[wi] & mask)], digits, digit_c);
             }
             e[c] = v;
         }
@@ -66,7 +80,7 @@ __global__ void pack_wide_tables_kernel(const uint16_t *__restrict__ lut16, cons
 // Transposed convolution: the phase blocks of pack_line_tables_convt_kernel in the wide order.
 __global__ void pack_wide_tables_convt_kernel(const uint16_t *__restrict__ lut16, const int8_t *__restrict__ w,
                                               uint4 *__restrict__ dt, int bits, int N, int Cin, int kh, int kw, int s, int Cp,
-                                              int n_tiles) {
+                                              int n_tiles, int digits, int digit_c) {
     const int lines = 1 << bits, mask = lines - 1;
     const int Ty = kh / s, Tx = kw / s, gpt = Cp / 32;
     const size_t per_table = (size_t)lines * 16;
@@ -95,7 +109,7 @@ __global__ void pack_wide_tables_convt_kernel(const uint16_t *__restrict__ lut16
             uint32_t v = 0;
             if (n < N && ci < Cin) {
                 const size_t wi = (((size_t)ci * N + n) * kh + ky) * kw + kx;
-                v = lut16[(size_t)a * lines + ((int)w[wi] & mask)];
+                v = wide_entry(lut16[(size_t)a * lines + ((int)w[wi] & mask)], digits, digit_c);
             }
             e[c] = v;
         }
@@ -112,9 +126,41 @@ __device__ __forceinline__ void wide_fetch(u32x4_t &v, uint32_t word, uint32_t c
                  : [wd] "v"(word), [cw] "v"(colw), [sl] "v"(sel));
 }
 
+// Digit tables (MF instantiations): the eight entries a lane has read are widened and added by the matrix pipe instead
+// of eight vector instructions.  v_mfma_i32_16x16x64_i8 computes D[i][j] += sum_k A[i][k] B[k][j]; lane l holds column
+// j = l % 16 of B for the 16 k of block l / 16, and afterwards rows 4 (l / 16) .. + 3 of column j of D.  With B = the 16
+// bytes the lane has read and an A that is zero outside the diagonal blocks (row 4 q + c only has weights in block q:
+// 1 and -128 on the two digit bytes of entry c, or of entry 4 + c for the second instruction), every lane gets the
+// four sums of ITS OWN entries back in its own registers.  The vector pipe keeps the address arithmetic, which runs
+// in the shadow of the matrix instructions (the dot instructions of the other form share the matrix pipe).
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ i32x4_t wide_mf_weights(int lane, int half) {
+    const int i = lane & 15, q = lane >> 4;
+    i32x4_t a = {0, 0, 0, 0};
+    if ((i >> 2) == q) {
+        const int e = (i & 3) + half * 4;
+        const uint32_t wt = (e & 1) ? 0x80010000u : 0x00008001u;
+        if ((e >> 1) == 0) a.x = (int)wt;
+        else if ((e >> 1) == 1) a.y = (int)wt;
+        else if ((e >> 1) == 2) a.z = (int)wt;
+        else a.w = (int)wt;
+    }
+    return a;
+}
+
+template <int WAITN>
+__device__ __forceinline__ void row_add_mf(i32x4_t &d0, i32x4_t &d1, u32x4_t &v, const i32x4_t &a0, const i32x4_t &a1) {
+    asm volatile("s_waitcnt lgkmcnt(%[wn])\n\t"
+                 "v_mfma_i32_16x16x64_i8 %[d0], %[a0], %[v], %[d0]\n\t"
+                 "v_mfma_i32_16x16x64_i8 %[d1], %[a1], %[v], %[d1]"
+                 : [d0] "+v"(d0), [d1] "+v"(d1)
+                 : [v] "v"(v), [a0] "v"(a0), [a1] "v"(a1), [wn] "n"(WAITN));
+}
+
 // DOPS: table copy operations per wave and step = 2^b * 256 B / (16 waves * 1 KB): 4 / 2 / 1 for b = 8 / 7 / <= 6
 // (smaller tables: one operation with fewer lanes).
-template <int DOPS, bool EXTRA = false>
+template <int DOPS, bool EXTRA = false, bool MF = false>
 __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const LinesParams p) {
     __shared__ __attribute__((aligned(256))) uint4 tbl[2 * (WIDE_BUF_BYTES / 16)];      // 128 KB
     const int tid = threadIdx.x;
@@ -253,21 +299,36 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const Lin
             sel[u][r] = 0x0c020000u | ((4u + 2u * (uint32_t)u + e) << 8);
         }
 
+    // digit tables: sums of row i in accm[2 i] (channels 0..3) and accm[2 i + 1] (channels 4..7)
+    i32x4_t accm[MF ? 16 : 1];
+#pragma unroll
+    for (int q = 0; q < (MF ? 16 : 1); ++q) accm[q] = i32x4_t{0, 0, 0, 0};
+    const i32x4_t mfa0 = wide_mf_weights(lane, 0), mfa1 = wide_mf_weights(lane, 1);
+    auto add_row = [&](auto rowc, auto waitc, u32x4_t &v) {
+        constexpr int row = decltype(rowc)::value, WN = decltype(waitc)::value;
+        if constexpr (MF) row_add_mf<WN>(accm[2 * row], accm[2 * row + 1], v, mfa0, mfa1);
+        else row_add<true, WN>(acc + row * 8, v);
+    };
+
     // one step: 16 row-reads (read r = 0: rows 0..7, then r = 1: rows 0..7), four in flight
     auto run_step = [&](auto uc) {
         constexpr int u = decltype(uc)::value;
 #pragma unroll
         for (int q = 0; q < 4; ++q) wide_fetch(rv[q], aw.row(q), colw[u][0], sel[u][0]);
-#pragma unroll
-        for (int q = 0; q < 12; ++q) {
-            row_add<true, 3>(acc + (q & 7) * 8, rv[q & 3]);
-            const int qn = q + 4;
+        auto body = [&](auto qc) {
+            constexpr int q = decltype(qc)::value;
+            add_row(std::integral_constant<int, (q & 7)>{}, std::integral_constant<int, 3>{}, rv[q & 3]);
+            constexpr int qn = q + 4;
             wide_fetch(rv[q & 3], aw.row(qn & 7), colw[u][qn >> 3], sel[u][qn >> 3]);
-        }
-        row_add<true, 3>(acc + 4 * 8, rv[0]);
-        row_add<true, 2>(acc + 5 * 8, rv[1]);
-        row_add<true, 1>(acc + 6 * 8, rv[2]);
-        row_add<true, 0>(acc + 7 * 8, rv[3]);
+        };
+        body(std::integral_constant<int, 0>{}); body(std::integral_constant<int, 1>{}); body(std::integral_constant<int, 2>{});
+        body(std::integral_constant<int, 3>{}); body(std::integral_constant<int, 4>{}); body(std::integral_constant<int, 5>{});
+        body(std::integral_constant<int, 6>{}); body(std::integral_constant<int, 7>{}); body(std::integral_constant<int, 8>{});
+        body(std::integral_constant<int, 9>{}); body(std::integral_constant<int, 10>{}); body(std::integral_constant<int, 11>{});
+        add_row(std::integral_constant<int, 4>{}, std::integral_constant<int, 3>{}, rv[0]);
+        add_row(std::integral_constant<int, 5>{}, std::integral_constant<int, 2>{}, rv[1]);
+        add_row(std::integral_constant<int, 6>{}, std::integral_constant<int, 1>{}, rv[2]);
+        add_row(std::integral_constant<int, 7>{}, std::integral_constant<int, 0>{}, rv[3]);
     };
 
     // prologue: table of step 0, activations of the first group
@@ -293,11 +354,24 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const Lin
 
     // Lane j ends with run (j & 1) of channels (j >> 1) and (j >> 1) + 4: the two lanes of a pair write 32 adjacent
     // bytes, and the 8 row slots of a wave a whole 256-byte stretch of one channel in one instruction.
+    if constexpr (MF) {
+        // the last matrix instructions have to leave the pipe before a vector instruction reads their registers
+        asm volatile("s_nop 15\n\ts_nop 15" : : : "memory");
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            acc[q * 4 + 0] = (uint32_t)accm[q].x; acc[q * 4 + 1] = (uint32_t)accm[q].y;
+            acc[q * 4 + 2] = (uint32_t)accm[q].z; acc[q * 4 + 3] = (uint32_t)accm[q].w;
+        }
+    }
     const int r0 = mt * 1024 + rs * 8;
     if (r0 + 8 > p.M) return;               // M is a multiple of 8 here; no barrier follows
     const int hq = j & 1, cq = j >> 1;
     uint32_t w[4][2];
     reduce_scatter<8>(acc, j, w);
+    if (MF && ks == 0) {                    // digit tables: the offset of the entries, once per output
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { w[i][0] += (uint32_t)p.corr; w[i][1] += (uint32_t)p.corr; }
+    }
     int img, a0, b0;
     row_pos(r0 + 4 * hq, img, a0, b0);
     // transposed convolution (EXTRA instantiation, zsum given): the phase's output pixels of this run of 4 are
