@@ -34,9 +34,9 @@ MODEL_CUS = 256
 MEASURED_TRAFFIC_BYTES = {2: (18576 * 2.0 + 8192 * 1.0 + 4646 * 2.0 + 2312 * 1.0) * 1024}
 # the product kernel alone (lut_lines_wide_kernel<4> at configuration 2), same runs
 MEASURED_KERNEL_TRAFFIC_BYTES = {2: (18576 * 2.0 + 8192 * 1.0) * 1024}
-# vector instructions per lookup of that kernel: SQ_INSTS_VALU 24 264 704 wave instructions x 64 lanes per launch of
-# 1 207 959 552 lookups (profiles/lut_lines_wide_config2.md)
-WIDE_VALU_PER_LOOKUP = 24264704 * 64 / 1207959552
+# clocks the matrix pipe of a SIMD is busy per v_mfma_i32_16x16x64_i8 (SQ_VALU_MFMA_BUSY_CYCLES / SQ_INSTS_VALU_MFMA_I8 of
+# that kernel, profiles/lut_lines_wide_config2.md)
+MFMA_16X16X64_CLOCKS = 16
 
 
 def _f(x):
@@ -265,6 +265,8 @@ def main():
                     "(rows beyond the baseline, not bench lines of record)")
     ap.add_argument("--bits", type=int, default=8, help="table bits for config 5 (6 or 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--prewarm-ms", type=float, default=300.0,
+                    help="untimed steps for this long before the warm-up steps, so that the device clocks have settled (0: none)")
     ap.add_argument("--eager", action="store_true", help="network configurations: launch kernel by kernel instead of replaying a HIP graph")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run three plain 64 MiB device-to-device copies (what FETCH_SIZE / WRITE_SIZE are scaled by)")
@@ -291,6 +293,13 @@ def main():
         return
     step, core, macs, name, _keep = build_step(args.config, args.bits, torch, B, gnet, wl, args.eager)
 
+    # bring the device to its running clocks before anything is measured (a cold GPU runs the first tens of
+    # milliseconds slower; the W warm-up steps of the small configurations are over in well under a millisecond)
+    t_pre = time.perf_counter()
+    while time.perf_counter() - t_pre < args.prewarm_ms * 1e-3:
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -330,12 +339,14 @@ def main():
             covers = "the product kernel alone (lut_lines_wide_kernel); call_ms_avg adds the call's quantise-and-copy kernel"
             if args.traffic_bytes is None:
                 traffic = MEASURED_KERNEL_TRAFFIC_BYTES.get(args.config)
-            # second bound of the same kernel: it issues WIDE_VALU_PER_LOOKUP vector instructions per lookup (counters in
-            # profiles/), 64 lanes per clock per compute unit
-            alu_peak = cus * 64 * MODEL_CLOCK_GHZ * 1e9 / WIDE_VALU_PER_LOOKUP
-            extra_bound = dict(alu_peak=alu_peak / 1e12, alu_frac=macs / (float(kms.mean()) * 1e-3) / alu_peak,
-                               alu_model=f"{cus} CUs x 64 lanes/clk x {MODEL_CLOCK_GHZ} GHz / {WIDE_VALU_PER_LOOKUP:.3f} vector "
-                                         "instructions per lookup (SQ_INSTS_VALU / lookups of this kernel)")
+            # second bound of the same kernel: the pipe that widens and adds the entries.  With a table whose range fits
+            # the digit form (this one does) that is the matrix pipe: two v_mfma_i32_16x16x64_i8 of 16 clocks per 512
+            # lookups of a wave, four SIMDs per compute unit
+            pipe_peak = cus * 4 * 512 / (2 * MFMA_16X16X64_CLOCKS) * MODEL_CLOCK_GHZ * 1e9
+            extra_bound = dict(pipe_bound="mfma (int8)", pipe_peak=pipe_peak / 1e12,
+                               pipe_frac=macs / (float(kms.mean()) * 1e-3) / pipe_peak,
+                               pipe_model=f"{cus} CUs x 4 SIMDs x 512 lookups per 2 v_mfma_i32_16x16x64_i8 of "
+                                          f"{MFMA_16X16X64_CLOCKS} clocks x {MODEL_CLOCK_GHZ} GHz")
         else:
             kms = call_ms
             covers = "every kernel of the table-lookup call"
@@ -373,7 +384,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": ("int8 operands, int16 table, int32 accumulate, fp32 scale" if args.config < 8 else
                   "int16 operands (12-bit), int32 table or function, int32 accumulate, fp32 scale"),
-        "data": "synthetic (seeded)",
+        "data": "synthetic (seeded)", "prewarm_ms": args.prewarm_ms,
         "config": {"workload": name, "lut_macs_per_step": macs},
         "roofline": roof,
     }

@@ -1591,6 +1591,33 @@ def test_grouped_layer_refusals(B):
     assert e.value.code == -1
 
 
+@pytest.mark.parametrize("lo,span", [(-32768, 32895), (-16384, 32895), (-128, 32895), (-20000, 32896), (-3, 7), (-32768, 65535)])
+def test_wide_kernel_table_ranges(B, lo, span):
+    """The big-layer kernel stores table entries as two int8 digits of (entry - offset) when the table's range allows
+    (span <= 32895) and as plain int16 otherwise: tables whose entries sit at both ends of such ranges, one entry wider
+    than the limit, tiny and full int16 ranges, on a layer shape that takes that kernel; sums bit-exact either way."""
+    bits = 8
+    rng = np.random.default_rng(abs(lo) + span)
+    hi = lo + span
+    lut = rng.integers(lo, hi + 1, size=(256, 256), dtype=np.int64)
+    lut[0, 0], lut[255, 255], lut[128, 128], lut[7, 200] = lo, hi, hi, lo      # both extremes present, also for operand 0
+    lut = lut.astype(np.int32)
+    L = B.Lut(lut, bits)
+    N, Cin, Cout, HW = 32, 32, 64, 32
+    x = wl.random_i8(rng, (N, Cin, HW, HW), bits, "gauss")
+    w = wl.random_i8(rng, (Cout, Cin, 3, 3), bits, "gauss")
+    want = orc.approx_conv2d(lut, bits, x, w, (1, 1), (1, 1), threads=orc.host_threads())
+    pw = B.adapt_weights_pack_conv2d(L, dev(w))
+    got = host(B.adapt_approx_conv2d_packed(pw, dev(x), (1, 1), (1, 1)))
+    assert (got == want).all()
+    # the same through the fused layer call (rescaling in the kernel's epilogue)
+    xf = rng.standard_normal((N, Cin, HW, HW)).astype(np.float32)
+    s_x = orc.scale_from_amax(orc.absmax(xf), bits)
+    acc = orc.approx_conv2d(lut, bits, orc.quantize(xf, s_x, bits), w, (1, 1), (1, 1), threads=orc.host_threads())
+    y = orc.dequant(acc, np.float32(1e-6), N, Cout, HW * HW).reshape(acc.shape)
+    assert bits_equal(host(B.adapt_conv2d_layer_f32(pw, dev(xf), s_x, np.float32(1e-6), (1, 1), (1, 1))), y)
+
+
 @pytest.mark.parametrize("seed", [31, 32])
 def test_random_chains_match_oracle(B, seed):
     """Seeded random pairs of convolution layers, the first writing the second's quantised input copy in its epilogue:
