@@ -789,10 +789,19 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
             else rc = launch_lines_r<2>(p, (unsigned)grid, sgn, regular, s);
         }
         if (split && rc == ADAPT_OK) {
-            adapt::reduce_partials_kernel<<<ew_grid(c.out_elems), adapt::EW_THREADS, 0, s>>>(
+            const int wo = io ? io->chain_wo : 1;
+            const bool chained = fuse && half == 0 && io->chain.buf;
+            // four elements per thread where planes (and, with a chained copy, rows) are whole quads and everything is aligned
+            const bool quads = fuse && half == 0 && c.out_elems < 0x7fffffffull && c.out_elems % 4 == 0 && c.out_inner % 4 == 0 &&
+                               c.out_inner < 0x7fffffffull && c.out_channels < 0x7fffffffull && (!chained || wo % 4 == 0) &&
+                               ((reinterpret_cast<uintptr_t>(c.partial) | reinterpret_cast<uintptr_t>(out) |
+                                 reinterpret_cast<uintptr_t>(io->resid)) & 15u) == 0;
+            const size_t threads_needed = quads ? c.out_elems / 4 : c.out_elems;
+            adapt::reduce_partials_kernel<<<ew_grid(threads_needed), adapt::EW_THREADS, 0, s>>>(
                 c.partial, pl.ksplit, c.out_elems, out, c.out_elems, half == 0 ? -1 : 16, (fuse && half == 0) ? 1 : 0, c.out_channels,
                 c.out_inner, fuse ? io->s_out : 1.0f, fuse ? io->s_out_vec : nullptr, fuse ? io->bias : nullptr, fuse ? io->resid : nullptr,
-                fuse ? io->act : 0, (fuse && half == 0) ? io->chain : adapt::ChainOut{}, io ? io->chain_wo : 1);
+                fuse ? io->act : 0, (fuse && half == 0) ? io->chain : adapt::ChainOut{}, wo, fast_div((uint32_t)(quads ? c.out_inner : 1)),
+                fast_div((uint32_t)(quads ? c.out_channels : 1)), fast_div((uint32_t)(quads && wo > 0 ? wo : 1)), quads ? 1 : 0);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) rc = fail(ADAPT_ERR_HIP, "reduce_partials launch: %s", hipGetErrorString(e));
         }

@@ -449,8 +449,50 @@ __global__ __launch_bounds__(EW_THREADS) void reduce_partials_kernel(const int32
                                                                      size_t channels, size_t inner, float scale,
                                                                      const float *__restrict__ scales,
                                                                      const float *__restrict__ bias, const float *__restrict__ resid,
-                                                                     int act, ChainOut chain, int chain_wo) {
+                                                                     int act, ChainOut chain, int chain_wo, FastDiv d_inner,
+                                                                     FastDiv d_ch, FastDiv d_wo, int quads) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    if (quads) {
+        // rescaled output, fewer than 2^31 elements, planes and rows that are multiples of four elements, 16-byte aligned
+        // buffers: four consecutive elements per thread (one channel, one row), index arithmetic in 32 bits by
+        // multiply-and-shift (the general loop below spends most of its time in 64-bit divisions)
+        const uint32_t n4 = (uint32_t)(n >> 2), stride4 = (uint32_t)(stride_elems >> 2);
+        const uint4 *part4 = reinterpret_cast<const uint4 *>(part);
+        const uint32_t inner32 = (uint32_t)inner, ch32 = (uint32_t)channels;
+        for (uint32_t q = blockIdx.x * EW_THREADS + threadIdx.x; q < n4; q += (uint32_t)stride) {
+            uint4 v = part4[q];
+            for (int k = 1; k < ks; ++k) {
+                const uint4 t = part4[(size_t)k * stride4 + q];
+                v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+            }
+            const uint32_t i = q * 4u;
+            const uint32_t plane = d_inner.div(i), img = d_ch.div(plane);
+            const uint32_t ch = plane - img * ch32, pix = i - plane * inner32;
+            const float sc = scales ? scales[ch] : scale;
+            float y[4] = {(float)(int32_t)v.x * sc, (float)(int32_t)v.y * sc, (float)(int32_t)v.z * sc, (float)(int32_t)v.w * sc};
+            if (bias) {
+                const float b = bias[ch];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) y[e] = y[e] + b;
+            }
+            if (resid) {
+                const float4 r = reinterpret_cast<const float4 *>(resid)[q];
+                y[0] = y[0] + r.x; y[1] = y[1] + r.y; y[2] = y[2] + r.z; y[3] = y[3] + r.w;
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (act == 1) y[e] = y[e] > 0.0f ? y[e] : 0.0f;
+                else if (act == 2) y[e] = tanh_spec(y[e]);
+            }
+            reinterpret_cast<float4 *>(out)[q] = make_float4(y[0], y[1], y[2], y[3]);
+            if (chain.buf) {
+                const uint32_t oy = d_wo.div(pix), ox = pix - oy * (uint32_t)chain_wo;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) chain.put((int)img, (int)ch, (int)oy, (int)ox + e, y[e]);
+            }
+        }
+        return;
+    }
     for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
         uint32_t v = 0;
         for (int k = 0; k < ks; ++k) v += (uint32_t)part[(size_t)k * stride_elems + i];
