@@ -1880,7 +1880,10 @@ int adapt_avgpool_hw_f32(const float *x_dev, float *y_dev, size_t NC, size_t HW,
     if ((!x_dev || !y_dev) && NC) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_avgpool_hw_f32: NULL pointer");
     if (HW == 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_avgpool_hw_f32: HW is 0");
     if (!NC) return ADAPT_OK;
-    adapt::avgpool_kernel<<<(unsigned)((NC + adapt::EW_THREADS - 1) / adapt::EW_THREADS), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, y_dev, NC, HW);
+    if (HW == 64 && (reinterpret_cast<uintptr_t>(x_dev) & 15u) == 0 && (NC + 63) / 64 <= 0x7fffffffull)
+        adapt::avgpool64_kernel<<<(unsigned)((NC + 63) / 64), 64, 0, (hipStream_t)stream>>>(x_dev, y_dev, NC);
+    else
+        adapt::avgpool_kernel<<<(unsigned)((NC + adapt::EW_THREADS - 1) / adapt::EW_THREADS), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, y_dev, NC, HW);
     HIP_TRY(hipGetLastError());
     return ADAPT_OK;
 }
@@ -1891,7 +1894,9 @@ int adapt_shortcut_a_f32(const float *x_dev, float *y_dev, int N, int Cin, int H
     if (!x_dev || !y_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_shortcut_a_f32: NULL pointer");
     if (x_dev == y_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_shortcut_a_f32: in-place not possible");
     const size_t total = (size_t)N * Cout * ((H + 1) / 2) * ((W + 1) / 2);
-    adapt::shortcut_a_kernel<<<ew_grid(total), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, y_dev, N, Cin, H, W, Cout);
+    const int fast = total < 0x7fffffffull && (size_t)N * Cin * H * W < 0x7fffffffull ? 1 : 0;
+    adapt::shortcut_a_kernel<<<ew_grid(total), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(
+        x_dev, y_dev, N, Cin, H, W, Cout, fast_div((uint32_t)((W + 1) / 2)), fast_div((uint32_t)((H + 1) / 2)), fast_div((uint32_t)Cout), fast);
     HIP_TRY(hipGetLastError());
     return ADAPT_OK;
 }

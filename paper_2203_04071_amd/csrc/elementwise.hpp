@@ -10,6 +10,17 @@ namespace adapt {
 
 constexpr int EW_THREADS = 256;
 
+// Division of a 31-bit number by a launch-invariant divisor as multiply + shift: q = (n * M) >> k with
+// k = 31 + ceil(log2 d), M = floor(2^k / d) + 1, exact for every n < 2^31 (the error term n / 2^k stays below 1 / d).
+// An integer division costs about 35 vector instructions (a 64-bit one several times that), and the copy and
+// element-wise kernels are bound by instruction count.
+struct FastDiv {
+    uint32_t M;
+    int k;
+    uint32_t d;
+    __device__ __forceinline__ uint32_t div(uint32_t n) const { return (uint32_t)(((uint64_t)n * M) >> k); }
+};
+
 __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, size_t n) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
@@ -255,11 +266,47 @@ __global__ __launch_bounds__(EW_THREADS) void avgpool_kernel(const float *__rest
     y[i] = s * inv;
 }
 
+// The same for planes of 64 elements (an 8 x 8 feature map), 64 planes per workgroup of 64 lanes: the planes are read
+// with coalesced 16-byte loads into LDS (row pitch 65 words, so that lane t summing plane t meets no bank conflict),
+// then every lane adds up its plane in the same sequential order as above.
+__global__ __launch_bounds__(64) void avgpool64_kernel(const float *__restrict__ x, float *__restrict__ y, size_t NC) {
+    __shared__ float tile[64 * 65];
+    const size_t p0 = (size_t)blockIdx.x * 64;
+    const int t = threadIdx.x;
+    const size_t planes = NC - p0 < 64 ? NC - p0 : 64;
+    const float4 *src = reinterpret_cast<const float4 *>(x + p0 * 64);
+    for (int q = t; q < (int)planes * 16; q += 64) {       // float4 q = plane q / 16, elements 4 (q % 16) ..
+        const float4 v = src[q];
+        float *d = tile + (q >> 4) * 65 + (q & 15) * 4;
+        d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+    }
+    __syncthreads();
+    if ((size_t)t >= planes) return;
+    const float inv = 1.0f / 64.0f;
+    float s = 0.0f;
+#pragma unroll 8
+    for (int j = 0; j < 64; ++j) s = s + tile[t * 65 + j];
+    y[p0 + t] = s * inv;
+}
+
 __global__ __launch_bounds__(EW_THREADS) void shortcut_a_kernel(const float *__restrict__ x, float *__restrict__ y,
-                                                                int N, int Cin, int H, int W, int Cout) {
+                                                                int N, int Cin, int H, int W, int Cout, FastDiv dwo, FastDiv dho,
+                                                                FastDiv dco, int fast) {
     const int Ho = (H + 1) / 2, Wo = (W + 1) / 2, padc = (Cout - Cin) / 2;
     const size_t total = (size_t)N * Cout * Ho * Wo;
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    if (fast) {         // fewer than 2^31 elements on both sides: 32-bit indices, divisions by multiply-and-shift
+        for (uint32_t i = blockIdx.x * EW_THREADS + threadIdx.x; i < (uint32_t)total; i += (uint32_t)stride) {
+            const uint32_t r1 = dwo.div(i), ox = i - r1 * (uint32_t)Wo;
+            const uint32_t r2 = dho.div(r1), oy = r1 - r2 * (uint32_t)Ho;
+            const uint32_t n = dco.div(r2), c = r2 - n * (uint32_t)Cout;
+            const int ci = (int)c - padc;
+            float v = 0.0f;
+            if (ci >= 0 && ci < Cin) v = x[((n * (uint32_t)Cin + (uint32_t)ci) * (uint32_t)H + 2u * oy) * (uint32_t)W + 2u * ox];
+            y[i] = v;
+        }
+        return;
+    }
     for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < total; i += stride) {
         const int ox = (int)(i % Wo);
         const int oy = (int)((i / Wo) % Ho);

@@ -38,16 +38,6 @@ typedef short short2_t __attribute__((ext_vector_type(2)));
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-// Division of a 31-bit number by a launch-invariant divisor as multiply + shift: q = (n * M) >> k with
-// k = 31 + ceil(log2 d), M = floor(2^k / d) + 1, exact for every n < 2^31 (the error term n / 2^k stays below 1 / d).
-// An integer division costs about 35 vector instructions, and the copy kernels below are bound by instruction count.
-struct FastDiv {
-    uint32_t M;
-    int k;
-    uint32_t d;
-    __device__ __forceinline__ uint32_t div(uint32_t n) const { return (uint32_t)(((uint64_t)n * M) >> k); }
-};
-
 // A layer's output written a second time as the NEXT convolution's input copy: quantised with that layer's activation
 // scale (the quantiser of Sec. III-A), as table line indices, at the element's place in the zero-padded x-major or
 // channel-last copy (see pad_channels_last_kernel) whose borders and padded channels were zeroed beforehand.  The next
