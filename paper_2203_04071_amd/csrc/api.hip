@@ -414,6 +414,8 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     return rc;
 }
 
+adapt::FastDiv fast_div(uint32_t d);
+
 // Grouped convolution with fewer than 8 output channels per group (depthwise and its relatives): direct form
 // io: whole-layer form (fp32 activations in, rescaled fp32 / chained output): only the tiled kernel has it, so the call is
 // refused with ADAPT_ERR_UNSUPPORTED when the shape does not take that kernel
@@ -493,11 +495,20 @@ int run_grouped(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t 
         p.tile_elems = (int)gt * p.cg * p.rows_in * p.Wr;
         p.wl_bytes = (int)wl_bytes;
         p.ntiles = (int)tiles(ro, gt);
+        {
+            const int K = p.cg * taps, Wo4 = (Wo + 3) / 4;
+            p.d_plane_in = fast_div((uint32_t)(p.rows_in * p.Wr)); p.d_Wr = fast_div((uint32_t)p.Wr);
+            p.d_ogK = fast_div((uint32_t)(p.og * K)); p.d_K = fast_div((uint32_t)K); p.d_taps = fast_div((uint32_t)taps);
+            p.d_kw = fast_div((uint32_t)kw);
+            p.d_npix = fast_div((uint32_t)(p.ro * Wo)); p.d_Wo = fast_div((uint32_t)Wo);
+            p.d_nstrip = fast_div((uint32_t)(p.ro * Wo4)); p.d_Wo4 = fast_div((uint32_t)Wo4);
+        }
         blocks = (size_t)p.ntiles < (size_t)cu ? (size_t)p.ntiles : (size_t)cu;
         lds = (size_t)lut->img_bytes + wl_bytes + (size_t)((p.tile_elems + 15) / 16 * 16);
     } else {
         // one workgroup per compute unit at most (the table image fills its LDS), fewer when there is little to do
         p.chain4 = 0; p.cpl = 1;
+        p.d_plane_in = p.d_Wr = p.d_ogK = p.d_K = p.d_taps = p.d_kw = p.d_npix = p.d_Wo = p.d_nstrip = p.d_Wo4 = fast_div(1u);
         p.gt = p.ro = p.n_chunks = p.rows_in = p.Wr = p.tile_elems = p.wl_bytes = p.ntiles = 0;
         blocks = (p.total + adapt::ROWS_THREADS * 4 - 1) / (adapt::ROWS_THREADS * 4);
         if (blocks > (size_t)cu) blocks = (size_t)cu;

@@ -43,6 +43,8 @@ struct GroupedParams {
     float scale;
     const float *scales, *bias;
     ChainOut chain;
+    // divisors of the per-lane set-up of the tiled kernel (two dozen integer divisions per lane were 5 us of every launch)
+    FastDiv d_plane_in, d_Wr, d_ogK, d_K, d_taps, d_kw, d_npix, d_Wo, d_nstrip, d_Wo4;
     int cpl;                // output channels per work item of the tiled kernel (a multiple of 4 when chain4)
     int chain4;             // every tile starts at a channel that is a multiple of 4 and the copy's rows are whole words
 };
@@ -132,31 +134,36 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_grouped_tiled_kernel(const G
 #pragma unroll
     for (int u = 0; u < GROUPED_PF; ++u) {
         const int idx = tid + u * ROWS_THREADS;
-        const int c = idx / plane_in, rem = idx - c * plane_in;
-        const int r = rem / p.Wr, xx = rem - r * p.Wr;
+        const int c = (int)p.d_plane_in.div((uint32_t)idx), rem = idx - c * plane_in;
+        const int r = (int)p.d_Wr.div((uint32_t)rem), xx = rem - r * p.Wr;
         el_r[u] = r;
         el_x[u] = xx - p.pw;
         el_off[u] = (c * p.H + r) * p.W + xx - p.pw;
     }
     uint32_t my_toff = 0;                       // tap offset of word tid (word = (group in block, oc, ci, ky, kx))
     if (tid < p.gt * p.og * K) {
-        const int gi = tid / (p.og * K), k = tid % K, ci = k / taps, tp = k - ci * taps;
-        const int ky = tp / p.kw, kx = tp - ky * p.kw;
+        const int gi = (int)p.d_ogK.div((uint32_t)tid), k = tid - (int)p.d_K.div((uint32_t)tid) * K;
+        const int ci = (int)p.d_taps.div((uint32_t)k), tp = k - ci * taps;
+        const int ky = (int)p.d_kw.div((uint32_t)tp), kx = tp - ky * p.kw;
         my_toff = (uint32_t)(((gi * p.cg + ci) * p.rows_in + ky * p.dh) * p.Wr + kx * p.dw) << GROUPED_TOFF_SHIFT;
     }
     // work items of a tile: (slot of cpl consecutive output channels, output row, output column), column fastest; lane
     // tid takes items tid, tid + 1024, ...: its first item and the step, decomposed once
     const int npix = p.ro * p.Wo;
-    const int it0_s = tid / npix, it0_r = (tid - it0_s * npix) / p.Wo, it0_x = tid - it0_s * npix - it0_r * p.Wo;
-    const int d_s = ROWS_THREADS / npix, d_r = (ROWS_THREADS - d_s * npix) / p.Wo, d_x = ROWS_THREADS - d_s * npix - d_r * p.Wo;
+    const int it0_s = (int)p.d_npix.div((uint32_t)tid), it0_r = (int)p.d_Wo.div((uint32_t)(tid - it0_s * npix));
+    const int it0_x = tid - it0_s * npix - it0_r * p.Wo;
+    const int d_s = (int)p.d_npix.div(ROWS_THREADS), d_r = (int)p.d_Wo.div((uint32_t)(ROWS_THREADS - d_s * npix));
+    const int d_x = ROWS_THREADS - d_s * npix - d_r * p.Wo;
 
     // strips (KW > 0): items (slot, row, strip of 4 columns), strip fastest; with the quad exchange the 4 lanes of a quad
     // share an item and differ in the channel (slot = 4 channels), otherwise slot = channel
     const int q4 = KW > 0 && p.chain4 ? 1 : 0, cl = q4 ? tid & 3 : 0;
     const int Wo4 = (p.Wo + 3) >> 2, nstrip = p.ro * Wo4;
     const int s_tid = q4 ? tid >> 2 : tid, s_step = q4 ? ROWS_THREADS >> 2 : ROWS_THREADS;
-    const int st0_s = s_tid / nstrip, st0_r = (s_tid - st0_s * nstrip) / Wo4, st0_x = s_tid - st0_s * nstrip - st0_r * Wo4;
-    const int sd_s = s_step / nstrip, sd_r = (s_step - sd_s * nstrip) / Wo4, sd_x = s_step - sd_s * nstrip - sd_r * Wo4;
+    const int st0_s = (int)p.d_nstrip.div((uint32_t)s_tid), st0_r = (int)p.d_Wo4.div((uint32_t)(s_tid - st0_s * nstrip));
+    const int st0_x = s_tid - st0_s * nstrip - st0_r * Wo4;
+    const int sd_s = (int)p.d_nstrip.div((uint32_t)s_step), sd_r = (int)p.d_Wo4.div((uint32_t)(s_step - sd_s * nstrip));
+    const int sd_x = s_step - sd_s * nstrip - sd_r * Wo4;
     const bool vec_out = (p.Wo & 3) == 0 && (reinterpret_cast<uintptr_t>(p.out) & 15u) == 0;                                   // 4 outputs of a strip = one aligned 16-byte store
 
     // Prefetch: the byte loads are issued from inline assembly and retired by an explicit wait just before their values
