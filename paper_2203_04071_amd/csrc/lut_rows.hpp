@@ -138,8 +138,11 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
+    // (MT and KS are powers of two, MT * KS = 1024: shifts instead of divisions, which cost tens of instructions each —
+    // noticeable in a kernel that is launched once per time step)
+    const int mt_log = __builtin_ctz((unsigned)p.MT), ks_log = 10 - mt_log;
     const int row_waves = p.MT >> 6;
-    const int ks = wave / row_waves;
+    const int ks = wave >> (mt_log - 6);
     const int rb = wave - ks * row_waves;
     const int r_in_tile = rb * 64 + lane;
     const int m = blockIdx.x * p.MT + r_in_tile;
@@ -147,17 +150,20 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
     const int mm = mvalid ? m : p.M - 1;
     const int n0 = blockIdx.y * NT;
 
-    const int img = mm / p.HoWo;
-    const int pix = mm - img * p.HoWo;
-    const int oy = pix / p.Wo;
-    const int ox = pix - oy * p.Wo;
+    int img = mm, pix = 0, oy = 0, ox = 0;          // linear layer: HoWo = Wo = 1
+    if (p.mode != MODE_GEMM) {
+        img = mm / p.HoWo;
+        pix = mm - img * p.HoWo;
+        oy = pix / p.Wo;
+        ox = pix - oy * p.Wo;
+    }
     const int grp = blockIdx.z;
     const int8_t *xb = p.x + (size_t)img * p.img_stride + (size_t)grp * p.Cin * p.kstride;
 
     const int Ktot = p.taps * p.Cin;
     const uint32_t *wofs = p.wofs + (size_t)grp * Ktot * p.Npad;
     const int ch0 = grp * p.N;              // first output channel of the group
-    const int kc = (Ktot + p.KS - 1) / p.KS;
+    const int kc = (Ktot + p.KS - 1) >> ks_log;
     int k = ks * kc;
     const int k_end = min(Ktot, k + kc);
 
@@ -283,7 +289,7 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
     if (NT == 2 && p.lstm == 3) {
         // one thread per (row, unit of the pair): the sum, then the plain recurrent cell (the operations of rnn_cell_kernel)
         for (int o = tid; o < 2 * p.MT; o += ROWS_THREADS) {
-            const int e = o / p.MT, r = o - e * p.MT;
+            const int e = o >> mt_log, r = o - e * p.MT;
             const int m2 = blockIdx.x * p.MT + r;
             if (m2 >= p.M) continue;
             const int u = blockIdx.y * 2 + e;
@@ -303,7 +309,7 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
     if (NT == 6 && p.lstm == 2) {
         // one thread per (row, unit of the pair): the three gate sums, then the GRU cell
         for (int o = tid; o < 2 * p.MT; o += ROWS_THREADS) {
-            const int e = o / p.MT, r = o - e * p.MT;
+            const int e = o >> mt_log, r = o - e * p.MT;
             const int m2 = blockIdx.x * p.MT + r;
             if (m2 >= p.M) continue;
             const int u = blockIdx.y * 2 + e;
@@ -336,7 +342,7 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
     if (NT == 8 && p.lstm == 1) {
         // one thread per (row, unit of the pair): the four gate sums, then the cell
         for (int o = tid; o < 2 * p.MT; o += ROWS_THREADS) {
-            const int e = o / p.MT, r = o - e * p.MT;
+            const int e = o >> mt_log, r = o - e * p.MT;
             const int m2 = blockIdx.x * p.MT + r;
             if (m2 >= p.M) continue;
             const int u = blockIdx.y * 2 + e;
@@ -367,12 +373,12 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
         return;
     }
     for (int o = tid; o < NT * p.MT; o += ROWS_THREADS) {
-        const int n = o / p.MT, r = o - n * p.MT;
+        const int n = o >> mt_log, r = o - n * p.MT;
         const int m2 = blockIdx.x * p.MT + r;
         if (m2 >= p.M || n0 + n >= p.N) continue;
         uint32_t s = 0;
         for (int j = 0; j < p.KS; ++j) s += red[((size_t)j * NT + n) * p.MT + r];
-        const int img2 = m2 / p.HoWo, pix2 = m2 - img2 * p.HoWo;
+        const int img2 = p.mode == MODE_GEMM ? m2 : m2 / p.HoWo, pix2 = m2 - img2 * p.HoWo;
         int32_t *q = p.out + (size_t)img2 * p.out_ch * p.HoWo + (size_t)(ch0 + n0 + n) * p.HoWo + pix2;
         if (p.shift < 0) *q = (int32_t)finish_sum(p, s, ch0 + n0 + n);
         else *q = (int32_t)((uint32_t)*q + (s << p.shift));
