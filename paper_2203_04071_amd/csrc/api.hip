@@ -750,6 +750,8 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     p.ch_stride = c.ch_stride;
     p.out_plane = c.out_plane; p.out_sy = c.out_sy; p.out_sx = c.out_sx;
     p.m_tiles = (c.M + 128 * R - 1) / (128 * R);
+    p.d_HoWo = fast_div((uint32_t)p.HoWo); p.d_Wo = fast_div((uint32_t)p.Wo);
+    p.d_ntiles = fast_div((uint32_t)p.n_tiles); p.d_mtiles = fast_div((uint32_t)p.m_tiles); p.d_phases = fast_div(1u);
     p.ksplit = pl.ksplit; p.gps = pl.gps; p.ks_out_stride = split ? (long long)c.out_elems : 0;
     // digit tables: every real lookup of an output lacks the offset (sums wrap in 32 bits like everything else)
     p.corr = c.wide_digits ? (int)(uint32_t)((unsigned long long)((long long)q.kh * q.kw * q.Cin * (long long)c.wide_c)) : 0;
@@ -791,6 +793,7 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
             }
             const long long grid = (long long)p.m_tiles * q.n_tiles * p.phases * p.ksplit;
             if (grid > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "lines path: grid too large");
+            p.d_phases = fast_div((uint32_t)p.phases);
             if (use_wide) {
                 p.dt = c.dt_wide;
                 rc = launch_lines_wide(p, (unsigned)grid, extra, c.wide_digits != 0, s);

@@ -100,6 +100,9 @@ struct LinesParams {
     // reduce_partials_kernel adds the slices up.  ksplit == 1: no split.
     int ksplit, gps;
     long long ks_out_stride;
+    // the divisions every lane (rows -> image, row, column) and every wave (workgroup id -> tiles) starts with, as
+    // multiply-and-shift: they were 1 - 2 us of every launch
+    FastDiv d_HoWo, d_Wo, d_ntiles, d_mtiles, d_phases;
     int corr;               // wide kernel with digit tables: added to every finished sum (see lut_wide.hpp); else 0
     // Tap pairing (fast kernel, PAIRED): layers with fewer than 32 (padded) channels per tap put pair_g = 32 / Cp taps
     // side by side in a group of four steps: k-sub j serves tap pair_g * group + j / pair_cg and the four channels
@@ -628,10 +631,10 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_kernel(const LinesPar
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = tid & 7;
     const int rs = tid >> 3;
-    const int nt = blockIdx.x % p.n_tiles;      // consecutive workgroup ids land on different XCDs:
-    const int wg = blockIdx.x / p.n_tiles;      // n-tile == id mod n_tiles keeps one table stream per XCD L2
-    const int mt = wg % p.m_tiles;
-    const int ph = wg / p.m_tiles;
+    const int wg = (int)p.d_ntiles.div(blockIdx.x);     // consecutive workgroup ids land on different XCDs:
+    const int nt = blockIdx.x - wg * p.n_tiles;         // n-tile == id mod n_tiles keeps one table stream per XCD L2
+    const int ph = (int)p.d_mtiles.div((uint32_t)wg);
+    const int mt = wg - ph * p.m_tiles;
     const int8_t *const xt = p.xt + pick4(p.xt_off, ph);
     const int out_off = pick4(p.out_off, ph);
     const int lines = 1 << p.bits;
@@ -652,8 +655,8 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_kernel(const LinesPar
         for (int i = 0; i < (REGULAR ? 1 : R); ++i) {
             int r = r0 + i;
             if (r >= p.M) r = p.M - 1;
-            const int img = r / p.HoWo, pix = r - img * p.HoWo;
-            const int oy = pix / p.Wo, ox = pix - oy * p.Wo;
+            const int img = (int)p.d_HoWo.div((uint32_t)r), pix = r - img * p.HoWo;
+            const int oy = (int)p.d_Wo.div((uint32_t)pix), ox = pix - oy * p.Wo;
             base[i] = (uint32_t)((long long)img * p.img_stride + (long long)oy * p.oy_stride + (long long)ox * p.ox_stride + j * p.Cc);
         }
         if (REGULAR) row_step = p.HoWo == 1 ? (uint32_t)p.img_stride : (uint32_t)p.ox_stride;
@@ -770,8 +773,8 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_kernel(const LinesPar
     for (int i = 0; i < R / 2; ++i) {
         const int r = mt * (128 * R) + rs * R + (R / 2) * (j & 1) + i;
         if (r >= p.M) continue;
-        const int img = r / p.HoWo, pix = r - img * p.HoWo;
-        const int a = pix / p.Wo, b = pix - a * p.Wo;
+        const int img = (int)p.d_HoWo.div((uint32_t)r), pix = r - img * p.HoWo;
+        const int a = (int)p.d_Wo.div((uint32_t)pix), b = pix - a * p.Wo;
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const int n = nt * 8 + (j >> 1) + 4 * t;
@@ -879,12 +882,12 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = tid & 7;
     const int rs = tid >> 3;
-    const int nt = blockIdx.x % p.n_tiles;
-    const int wg = blockIdx.x / p.n_tiles;
-    const int mt = wg % p.m_tiles;
-    const int pk = wg / p.m_tiles;
-    const int ph = pk % p.phases;
-    const int ks = pk / p.phases;               // slice of the inner dimension
+    const int wg = (int)p.d_ntiles.div(blockIdx.x);
+    const int nt = blockIdx.x - wg * p.n_tiles;
+    const int pk = (int)p.d_mtiles.div((uint32_t)wg);
+    const int mt = wg - pk * p.m_tiles;
+    const int ks = (int)p.d_phases.div((uint32_t)pk);   // slice of the inner dimension
+    const int ph = pk - ks * p.phases;
     const int8_t *const xt = p.xt + pick4(p.xt_off, ph);
     const int out_off = pick4(p.out_off, ph);
     int32_t *const outp = p.out + (size_t)ks * p.ks_out_stride;
@@ -935,9 +938,9 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
     // position of row r: image, output row a, output column b; the run after an x-major run of 4 pixels follows
     // without further divisions (Wo and HoWo are multiples of 4 there)
     auto row_pos = [&](int r, int &img, int &a, int &b) {
-        img = r / p.HoWo;
+        img = (int)p.d_HoWo.div((uint32_t)r);
         const int pix = r - img * p.HoWo;
-        a = pix / p.Wo;
+        a = (int)p.d_Wo.div((uint32_t)pix);
         b = pix - a * p.Wo;
     };
     auto next_run = [&](int &img, int &a, int &b) {
@@ -1174,15 +1177,15 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
         }
     } else {
         int img0 = 0, pix0 = 0;
-        if (REGULAR) { img0 = r0 / p.HoWo; pix0 = r0 - img0 * p.HoWo; }
+        if (REGULAR) { img0 = (int)p.d_HoWo.div((uint32_t)r0); pix0 = r0 - img0 * p.HoWo; }
 #pragma unroll
         for (int i = 0; i < R / 2; ++i) {
             const int r = r0 + i;
             if (r >= p.M) continue;
             int img, pix;
             if (REGULAR && p.HoWo > 1) { img = img0; pix = pix0 + i; }      // consecutive pixels of one output row
-            else { img = r / p.HoWo; pix = r - img * p.HoWo; }
-            const int a = pix / p.Wo, b = pix - a * p.Wo;
+            else { img = (int)p.d_HoWo.div((uint32_t)r); pix = r - img * p.HoWo; }
+            const int a = (int)p.d_Wo.div((uint32_t)pix), b = pix - a * p.Wo;
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 const int n = nt * 8 + (j >> 1) + 4 * t;

@@ -168,12 +168,12 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const Lin
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = tid & 7;
     const int rs = tid >> 3;
-    const int nt = blockIdx.x % p.n_tiles;
-    const int wg = blockIdx.x / p.n_tiles;
-    const int mt = wg % p.m_tiles;
-    const int pk = wg / p.m_tiles;
-    const int ph = pk % p.phases;
-    const int ks = pk / p.phases;
+    const int wg = (int)p.d_ntiles.div(blockIdx.x);
+    const int nt = blockIdx.x - wg * p.n_tiles;
+    const int pk = (int)p.d_mtiles.div((uint32_t)wg);
+    const int mt = wg - pk * p.m_tiles;
+    const int ks = (int)p.d_phases.div((uint32_t)pk);
+    const int ph = pk - ks * p.phases;
     const int8_t *const xt = p.xt + pick4(p.xt_off, ph);
     const int out_off = pick4(p.out_off, ph);
     int32_t *const outp = p.out + (size_t)ks * p.ks_out_stride;
@@ -210,9 +210,9 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const Lin
 
     // activation side: exactly the x-major addressing of lut_lines_fast_kernel, with 32 consecutive channels per group
     auto row_pos = [&](int r, int &img, int &a, int &b) {
-        img = r / p.HoWo;
+        img = (int)p.d_HoWo.div((uint32_t)r);
         const int pix = r - img * p.HoWo;
-        a = pix / p.Wo;
+        a = (int)p.d_Wo.div((uint32_t)pix);
         b = pix - a * p.Wo;
     };
     auto next_run = [&](int &img, int &a, int &b) {
