@@ -50,16 +50,19 @@ struct ChainOut {
     // element (image, channel c, row oy, column ox) of the producing layer's fp32 output y
     __device__ __forceinline__ void put(int img, int c, int oy, int ox, float y) const {
         const uint32_t q = (uint32_t)quant1(y, scale, Q) & mask;
-        const size_t row = (size_t)img * Hp + oy + ph;
-        const size_t a = xmajor ? ((row * (Cp >> 2) + (c >> 2)) * Wp + ox + pw) * 4 + (c & 3) : (row * Wp + ox + pw) * Cp + c;
+        // (a copy is smaller than 2^31 bytes: 32-bit offsets)
+        const uint32_t row = (uint32_t)img * (uint32_t)Hp + (uint32_t)(oy + ph), col = (uint32_t)(ox + pw);
+        const uint32_t a = xmajor ? ((row * (uint32_t)(Cp >> 2) + (uint32_t)(c >> 2)) * (uint32_t)Wp + col) * 4u + (uint32_t)(c & 3)
+                                  : (row * (uint32_t)Wp + col) * (uint32_t)Cp + (uint32_t)c;
         buf[a] = (int8_t)q;
     }
     // the same for channels c .. c + 3 (c a multiple of 4, Cp a multiple of 4) of one pixel: they are one aligned word
     // of either copy
     __device__ __forceinline__ uint32_t code(float y) const { return (uint32_t)quant1(y, scale, Q) & mask; }
     __device__ __forceinline__ void put4(int img, int c, int oy, int ox, uint32_t codes) const {
-        const size_t row = (size_t)img * Hp + oy + ph;
-        const size_t a = xmajor ? ((row * (Cp >> 2) + (c >> 2)) * Wp + ox + pw) * 4 : (row * Wp + ox + pw) * Cp + c;
+        const uint32_t row = (uint32_t)img * (uint32_t)Hp + (uint32_t)(oy + ph), col = (uint32_t)(ox + pw);
+        const uint32_t a = xmajor ? ((row * (uint32_t)(Cp >> 2) + (uint32_t)(c >> 2)) * (uint32_t)Wp + col) * 4u
+                                  : (row * (uint32_t)Wp + col) * (uint32_t)Cp + (uint32_t)c;
         *reinterpret_cast<uint32_t *>(buf + a) = codes;
     }
 };
