@@ -265,6 +265,33 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
         k += cnt;
     }
 
+    // Time-step kernels: thread tid < 2 MT (MT = 64 there) runs the cell of (row tid % MT, unit tid / MT of the
+    // workgroup's pair) after the reduction.  What the cell reads besides the sums — the step's input products, the
+    // previous c or h — comes from memory not touched before in this step; it is requested here, when this wave has
+    // finished its lookups, and arrives while the workgroup meets at the barriers and the sums are reduced.  (Requested
+    // earlier, before or during the lookups, the same loads made the LSTM step slower every time it was tried.)
+    constexpr int CELL_G = NT == 8 ? 4 : (NT == 6 ? 3 : 1);
+    const int cell_e = tid >> mt_log, cell_r = tid - cell_e * p.MT, cell_m = blockIdx.x * p.MT + cell_r;
+    const bool cell_thread = (NT == 8 || NT == 6 || NT == 2) && p.lstm != 0 && tid < 2 * p.MT && cell_m < p.M;
+    int32_t cell_ih[4] = {0, 0, 0, 0};
+    float cell_prev = 0.0f, cell_b[4] = {0.0f, 0.0f, 0.0f, 0.0f}, cell_b2[3] = {0.0f, 0.0f, 0.0f};
+    asm volatile("" : : : "memory");        // (keeps the loads below from being moved up into the loops)
+    if (cell_thread) {
+        const int u = blockIdx.y * 2 + cell_e;
+#pragma unroll
+        for (int g = 0; g < CELL_G; ++g) cell_ih[g] = p.acc_ih[(size_t)cell_m * CELL_G * p.Hs + (size_t)g * p.Hs + u];
+        if (NT == 8) cell_prev = p.c[(size_t)cell_m * p.Hs + u];
+        else if (NT == 6) cell_prev = p.h_prev[(size_t)cell_m * p.Hs + u];
+        if (p.bias) {
+#pragma unroll
+            for (int g = 0; g < CELL_G; ++g) cell_b[g] = p.bias[g * p.Hs + u];
+        }
+        if (NT == 6 && p.bias_hh) {
+#pragma unroll
+            for (int g = 0; g < 3; ++g) cell_b2[g] = p.bias_hh[g * p.Hs + u];
+        }
+    }
+
     if (p.KS == 1) {
         if (mvalid) {
             int32_t *o = p.out + (size_t)img * p.out_ch * p.HoWo + pix;
@@ -289,6 +316,11 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
     if (NT == 2 && p.lstm == 3) {
         // one thread per (row, unit of the pair): the sum, then the plain recurrent cell (the operations of rnn_cell_kernel)
         for (int o = tid; o < 2 * p.MT; o += ROWS_THREADS) {
+            // (empty statements: without them the compiler converts the values requested above to fp32 right behind their
+            // loads, i.e. waits for them before the barriers)
+#pragma unroll
+            for (int g = 0; g < CELL_G; ++g) asm volatile("" : "+v"(cell_ih[g]));
+            asm volatile("" : "+v"(cell_prev));
             const int e = o >> mt_log, r = o - e * p.MT;
             const int m2 = blockIdx.x * p.MT + r;
             if (m2 >= p.M) continue;
@@ -296,10 +328,10 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
             const size_t ci = (size_t)m2 * p.Hs + u;
             uint32_t s = 0;
             for (int j = 0; j < p.KS; ++j) s += red[((size_t)j * NT + e) * p.MT + r];
-            const float uu = (float)p.acc_ih[ci] * p.s_ih;
+            const float uu = (float)cell_ih[0] * p.s_ih;
             const float vv = (float)(int32_t)s * p.s_hh;
             float t = uu + vv;
-            t = t + (p.bias ? p.bias[u] : 0.0f);
+            t = t + (p.bias ? cell_b[0] : 0.0f);
             const float hn = p.act == 1 ? (t > 0.0f ? t : 0.0f) : tanh_spec(t);
             p.h[ci] = hn;
             p.qh_next[ci] = (int8_t)quant1(hn, p.s_h, p.Qh);
@@ -309,6 +341,11 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
     if (NT == 6 && p.lstm == 2) {
         // one thread per (row, unit of the pair): the three gate sums, then the GRU cell
         for (int o = tid; o < 2 * p.MT; o += ROWS_THREADS) {
+            // (empty statements: without them the compiler converts the values requested above to fp32 right behind their
+            // loads, i.e. waits for them before the barriers)
+#pragma unroll
+            for (int g = 0; g < CELL_G; ++g) asm volatile("" : "+v"(cell_ih[g]));
+            asm volatile("" : "+v"(cell_prev));
             const int e = o >> mt_log, r = o - e * p.MT;
             const int m2 = blockIdx.x * p.MT + r;
             if (m2 >= p.M) continue;
@@ -319,10 +356,10 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
             for (int g = 0; g < 3; ++g) {
                 uint32_t s = 0;
                 for (int j = 0; j < p.KS; ++j) s += red[((size_t)j * NT + g * 2 + e) * p.MT + r];
-                float uu = (float)p.acc_ih[(size_t)m2 * 3 * p.Hs + (size_t)g * p.Hs + u] * p.s_ih;
-                if (p.bias) uu = uu + p.bias[g * p.Hs + u];
+                float uu = (float)cell_ih[g] * p.s_ih;
+                if (p.bias) uu = uu + cell_b[g];
                 float vv = (float)(int32_t)s * p.s_hh;
-                if (p.bias_hh) vv = vv + p.bias_hh[g * p.Hs + u];
+                if (p.bias_hh) vv = vv + cell_b2[g];
                 gi[g] = uu;
                 gh[g] = vv;
             }
@@ -332,7 +369,7 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
             const float ng = tanh_spec(gi[2] + rn);
             const float omz = 1.0f - zg;
             const float t0 = omz * ng;
-            const float t1 = zg * p.h_prev[ci];
+            const float t1 = zg * cell_prev;
             const float hn = t0 + t1;
             p.h[ci] = hn;
             p.qh_next[ci] = (int8_t)quant1(hn, p.s_h, p.Qh);
@@ -342,6 +379,11 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
     if (NT == 8 && p.lstm == 1) {
         // one thread per (row, unit of the pair): the four gate sums, then the cell
         for (int o = tid; o < 2 * p.MT; o += ROWS_THREADS) {
+            // (empty statements: without them the compiler converts the values requested above to fp32 right behind their
+            // loads, i.e. waits for them before the barriers)
+#pragma unroll
+            for (int g = 0; g < CELL_G; ++g) asm volatile("" : "+v"(cell_ih[g]));
+            asm volatile("" : "+v"(cell_prev));
             const int e = o >> mt_log, r = o - e * p.MT;
             const int m2 = blockIdx.x * p.MT + r;
             if (m2 >= p.M) continue;
@@ -352,17 +394,17 @@ __global__ __launch_bounds__(ROWS_THREADS) void lut_rows_kernel(const RowsParams
             for (int g = 0; g < 4; ++g) {
                 uint32_t s = 0;
                 for (int j = 0; j < p.KS; ++j) s += red[((size_t)j * NT + g * 2 + e) * p.MT + r];
-                const float uu = (float)p.acc_ih[(size_t)m2 * 4 * p.Hs + (size_t)g * p.Hs + u] * p.s_ih;
+                const float uu = (float)cell_ih[g] * p.s_ih;
                 const float vv = (float)(int32_t)s * p.s_hh;
                 float t = uu + vv;
-                t = t + (p.bias ? p.bias[g * p.Hs + u] : 0.0f);
+                t = t + (p.bias ? cell_b[g] : 0.0f);
                 pre[g] = t;
             }
             const float ig = sigmoid_spec(pre[0]);
             const float fg = sigmoid_spec(pre[1]);
             const float gg = tanh_spec(pre[2]);
             const float og = sigmoid_spec(pre[3]);
-            const float fc = fg * p.c[ci];
+            const float fc = fg * cell_prev;
             const float igg = ig * gg;
             const float cn = fc + igg;
             p.c[ci] = cn;
