@@ -866,6 +866,19 @@ int launch_pad(const LayerIO *io, const int8_t *x, int bits, int8_t *xt, int N, 
     if (!blocks) return ADAPT_OK;
     const adapt::FastDiv dwp = fast_div((uint32_t)(W + 2 * pw)), dc4 = fast_div((uint32_t)(Cp / 4)), dhp = fast_div((uint32_t)(H + 2 * ph));
     const int fast = total < 0x7fffffffull ? 1 : 0;
+    if (fast && (size_t)N * C * H * W < 0x7fffffffull && total * 4 < 0x7fffffffull && !getenv("ADAPT_PAD_SINGLE")) {
+        // several words per thread, all operands in flight together
+        constexpr int U = 2;
+        const unsigned mblocks = (unsigned)(((total + U - 1) / U + 255) / 256);
+        if (io && io->xf)
+            adapt::pad_channels_last_multi_kernel<adapt::SrcF32, U><<<mblocks, 256, 0, s>>>(
+                adapt::SrcF32{io->xf, io->s_x, io->Q, (1u << bits) - 1u}, xt, C, H, W, ph, pw, Cp, xmajor, dwp, dc4, dhp, (uint32_t)total);
+        else
+            adapt::pad_channels_last_multi_kernel<adapt::SrcI8, U><<<mblocks, 256, 0, s>>>(adapt::SrcI8{x, (1u << bits) - 1u}, xt, C, H, W, ph, pw,
+                                                                                           Cp, xmajor, dwp, dc4, dhp, (uint32_t)total);
+        HIP_TRY(hipGetLastError());
+        return ADAPT_OK;
+    }
     if (io && io->xf)
         adapt::pad_channels_last_kernel<<<(unsigned)blocks, 256, 0, s>>>(adapt::SrcF32{io->xf, io->s_x, io->Q, (1u << bits) - 1u}, xt, N, C, H, W,
                                                                          ph, pw, Cp, xmajor, dwp, dc4, dhp, fast);

@@ -165,16 +165,23 @@ __device__ __forceinline__ T pick4(const T *v, int i) {
 // quantize_kernel (Sec. III-A), so that a layer needs no separate quantisation pass.  The copies hold table line
 // indices (the kernels that extract a bit field do not care, the wide-line kernel relies on it).
 // byte(): the operand as a table line index, i.e. its two's-complement bits below 2^b (mask = 2^b - 1)
+// load() / code(): the two halves of byte(), for kernels that request several operands before they convert the first
 struct SrcI8 {
+    typedef int8_t raw_t;
     const int8_t *x;
     uint32_t mask;
     __device__ __forceinline__ uint32_t byte(size_t i) const { return (uint32_t)(uint8_t)x[i] & mask; }
+    __device__ __forceinline__ raw_t load(uint32_t i) const { return x[i]; }
+    __device__ __forceinline__ uint32_t code(raw_t v) const { return (uint32_t)(uint8_t)v & mask; }
 };
 struct SrcF32 {
+    typedef float raw_t;
     const float *x;
     float scale, Q;
     uint32_t mask;
     __device__ __forceinline__ uint32_t byte(size_t i) const { return (uint32_t)quant1(x[i], scale, Q) & mask; }
+    __device__ __forceinline__ raw_t load(uint32_t i) const { return x[i]; }
+    __device__ __forceinline__ uint32_t code(raw_t v) const { return (uint32_t)quant1(v, scale, Q) & mask; }
 };
 
 // NCHW int8 -> zero-padded copy, Cp (a multiple of 8) channels per pixel, in one of two orders:
@@ -219,6 +226,47 @@ __global__ void pad_channels_last_kernel(const Src x, int8_t *__restrict__ xt, i
         }
         if (xmajor) *reinterpret_cast<uint32_t *>(xt + i * 4) = v;
         else *reinterpret_cast<uint32_t *>(xt + (((size_t)n * Hp + yp) * Wp + xp) * Cp + c4 * 4) = v;
+    }
+}
+
+// The same copy for tensors of fewer than 2^31 elements on both sides, U output words per thread (word t, t + threads,
+// ...): all 4 U operands are requested before the first is converted.  One word per thread makes 9 waves per SIMD at
+// the benchmark layer, one more than fit at a time, so part of the copy waited for a second round of waves (one
+// memory round trip each); with two words per thread everything is resident at once and in flight together
+// (measured: 7.0 against 7.6 - 8.4 us; three words the same, six words no gain).
+template <typename Src, int U>
+__global__ __launch_bounds__(256) void pad_channels_last_multi_kernel(const Src x, int8_t *__restrict__ xt, int C, int H, int W, int ph,
+                                                                      int pw, int Cp, int xmajor, FastDiv dwp, FastDiv dc4,
+                                                                      FastDiv dhp, uint32_t total) {
+    const uint32_t threads = gridDim.x * 256u, t = blockIdx.x * 256u + threadIdx.x;
+    const uint32_t HW = (uint32_t)H * (uint32_t)W;
+    typename Src::raw_t raw[U][4];
+    uint32_t dst[U];
+    bool live[U], have[U][4];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t i = t + (uint32_t)u * threads;
+        live[u] = i < total;
+        const uint32_t ii = live[u] ? i : 0u;
+        const uint32_t r1 = dwp.div(ii), xp = ii - r1 * dwp.d;
+        const uint32_t r2 = dc4.div(r1), c4 = r1 - r2 * dc4.d;
+        const uint32_t n = dhp.div(r2), yp = r2 - n * dhp.d;
+        const int y = (int)yp - ph, xx = (int)xp - pw;
+        const bool inside = live[u] && y >= 0 && y < H && xx >= 0 && xx < W;
+        const uint32_t src = ((n * (uint32_t)C + c4 * 4u) * (uint32_t)H + (uint32_t)(inside ? y : 0)) * (uint32_t)W + (uint32_t)(inside ? xx : 0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            have[u][q] = inside && (int)(c4 * 4u) + q < C;
+            raw[u][q] = x.load(have[u][q] ? src + (uint32_t)q * HW : 0u);
+        }
+        dst[u] = xmajor ? ii * 4u : ((n * dhp.d + yp) * dwp.d + xp) * (uint32_t)Cp + c4 * 4u;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        uint32_t v = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v |= (have[u][q] ? x.code(raw[u][q]) : 0u) << (8 * q);
+        if (live[u]) *reinterpret_cast<uint32_t *>(xt + dst[u]) = v;
     }
 }
 
