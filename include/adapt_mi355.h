@@ -292,6 +292,22 @@ int adapt_rnn_cell_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, flo
                        const float *bias_dev, int relu, float *h_dev, int8_t *qh_dev, float s_h, int bits, int B, int Hs,
                        void *stream);
 
+/* Chained transposed convolutions (the generator networks of Sec. V are stacks of them): as adapt_conv2d_chain_prepare /
+ * adapt_conv2d_layer_chain_f32, for handles of adapt_weights_pack_conv_transpose2d.
+ * adapt_conv_transpose2d_chain_prepare fixes the place and layout of h's input copy for inputs [N][Cin][H][W] and padding
+ * `pad` and zeroes it; afterwards a layer whose `next` is h writes its output there, and h runs with x_dev == NULL.
+ * Only geometries that take the phase form (filter sizes multiples of the stride, 2 pad a multiple of it, more than
+ * one input pixel) can be prepared: ADAPT_ERR_UNSUPPORTED otherwise.
+ * adapt_conv_transpose2d_layer_chain_f32: adapt_conv_transpose2d_layer_f32 with x_dev == NULL allowed (prepared handle)
+ * and, when next != NULL (a prepared conv2d or transposed-conv2d handle whose input is this layer's output), the output
+ * also written as next's quantised input copy with scale s_next.  y_dev is always written.  Every geometry is accepted
+ * as a producer. */
+int adapt_conv_transpose2d_chain_prepare(const adapt_weights *h, int N, int H, int W, int pad, void *stream);
+int adapt_conv_transpose2d_layer_chain_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W,
+                                           int pad, float s_x, float s_out, const float *s_out_vec_dev,
+                                           const float *bias_dev, int act, const adapt_weights *next, float s_next,
+                                           void *stream);
+
 /* One whole time step of the recurrent part of an LSTM layer in one kernel:
  *     acc_hh = table product of qh_dev [B][Hs] with the packed W_hh [4 Hs][Hs]   (adapt_approx_linear_packed)
  *     (c, h) = cell(acc_ih, acc_hh);  qh_next = quantise(h, s_h)                   (adapt_lstm_cell_q_f32)

@@ -30,6 +30,7 @@ EXPORTS = [
     "adapt_weights_destroy",
     "adapt_approx_linear_packed", "adapt_approx_conv2d_packed", "adapt_approx_conv_transpose2d_packed",
     "adapt_linear_layer_f32", "adapt_conv2d_layer_f32", "adapt_conv_transpose2d_layer_f32",
+    "adapt_conv_transpose2d_chain_prepare", "adapt_conv_transpose2d_layer_chain_f32",
     "adapt_conv2d_chain_prepare", "adapt_conv2d_layer_chain_f32", "adapt_conv2d_grouped_layer_f32",
     "adapt_relu_f32", "adapt_add_f32", "adapt_avgpool_hw_f32", "adapt_shortcut_a_f32",
     "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32", "adapt_lstm_cell_q_f32", "adapt_lstm_step_f32", "adapt_gru_step_f32", "adapt_rnn_step_f32", "adapt_gru_cell_f32", "adapt_rnn_cell_f32",
@@ -96,6 +97,8 @@ def load() -> ctypes.CDLL:
     L.adapt_conv2d_grouped_layer_f32.argtypes = [vp, vp, vp, vp] + [i32] * 14 + [f32, f32, vp, vp, i32, vp, f32, vp]
     L.adapt_conv2d_layer_chain_f32.argtypes = [vp, vp, vp] + [i32] * 9 + [f32, f32, vp, vp, vp, i32, vp, f32, vp]
     L.adapt_conv_transpose2d_layer_f32.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, f32, vp, vp, i32, vp]
+    L.adapt_conv_transpose2d_chain_prepare.argtypes = [vp, i32, i32, i32, i32, vp]
+    L.adapt_conv_transpose2d_layer_chain_f32.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, f32, vp, vp, i32, vp, f32, vp]
     L.adapt_approx_linear_packed.argtypes = [vp, vp, vp, i32, vp]
     L.adapt_approx_conv2d_packed.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
     L.adapt_relu_f32.argtypes = [vp, vp, sz, vp]
@@ -595,6 +598,27 @@ def adapt_conv_transpose2d_layer_f32(pw: PackedWeights, x, s_x, s_out, pad=0, bi
     sc, sv = _scales(s_out)
     _chk(load().adapt_conv_transpose2d_layer_f32(pw.handle, _ptr(x, torch.float32), _ptr(out, torch.float32), N, H, W, pad,
                                                  float(s_x), sc, sv, _ptr(bias, torch.float32), act, _stream(stream)))
+    return out
+
+
+def adapt_conv_transpose2d_chain_prepare(pw: PackedWeights, N, H, W, pad=0, stream=None):
+    """Raises AdaptError with code -2 (UNSUPPORTED) for geometries outside the phase form."""
+    assert pw.kind == "conv_transpose2d"
+    _chk(load().adapt_conv_transpose2d_chain_prepare(pw.handle, N, H, W, pad, _stream(stream)))
+
+
+def adapt_conv_transpose2d_layer_chain_f32(pw: PackedWeights, x, s_x, s_out, out, pad=0, bias=None, act=ACT_NONE,
+                                           next_pw: PackedWeights = None, s_next: float = 1.0, in_shape=None, stream=None):
+    """x None: the input copy is already in pw's prepared workspace (in_shape = (N, H, W) then); next_pw: also write the
+    output as next_pw's input copy, quantised with s_next.  `out` (fp32 [N][Cout][Ho][Wo]) is required."""
+    if x is not None:
+        N, Cin, H, W = x.shape
+    else:
+        N, H, W = in_shape
+    sc, sv = _scales(s_out)
+    _chk(load().adapt_conv_transpose2d_layer_chain_f32(pw.handle, _ptr(x, torch.float32), _ptr(out, torch.float32), N, H, W, pad,
+                                                       float(s_x), sc, sv, _ptr(bias, torch.float32), act,
+                                                       next_pw.handle if next_pw is not None else None, float(s_next), _stream(stream)))
     return out
 
 

@@ -89,7 +89,7 @@ struct LayerIO {
     adapt::ChainOut chain{};            // also write the output as the next convolution's quantised input copy (buf != nullptr)
     int chain_wo = 1;                   // width of the output (for the kernels that walk it element by element)
     // rescaling inside the product kernel needs a single table pass and an activation it knows
-    bool fused(int storage) const { return deq && storage == 0 && act <= 1; }
+    bool fused(int storage) const { return deq && storage == 0 && act <= 1 && !chain.buf; }
 };
 
 int finish_inplace(int32_t *buf, size_t n, size_t channels, size_t inner, const LayerIO &io, hipStream_t s) {
@@ -1011,7 +1011,7 @@ LinesShape convt_phase_shape(int bits, int Cout, int Cin, int kh, int kw, int st
 
 int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int32_t *zsum, const int8_t *x,
                            int32_t *out, int N, int H, int W, int kh, int kw, int st, int pad, hipStream_t s, Workspace *ws,
-                           const LayerIO *io = nullptr, const adapt_weights *wh = nullptr) {
+                           const LayerIO *io = nullptr, const adapt_weights *wh = nullptr, bool input_ready = false) {
     const int Ty = q.kh, Tx = q.kw, Cp = q.Cp;
     const int Hp = H + 2 * (Ty - 1), Wp = W + 2 * (Tx - 1);
     const int Ho = (H - 1) * st - 2 * pad + kh, Wo = (W - 1) * st - 2 * pad + kw;
@@ -1023,7 +1023,12 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
     const size_t part_bytes = lines_partial_bytes(M, q.n_tiles * st * st, q.Cc, Ty * Tx, out_elems);
     const size_t copy_bytes = ((xt_bytes + 64 + 255) / 256) * 256;
     int8_t *xt = nullptr;
-    {
+    if (input_ready) {          // the layer before wrote the copy (adapt_conv_transpose2d_chain_prepare fixed its place and layout)
+        if (!ws || !ws->ptr || ws->bytes < copy_bytes + part_bytes || !wh || wh->chain_in.xmajor != xmajor)
+            return fail(ADAPT_ERR_INVALID_ARGUMENT, "chained transposed convolution: the input buffer was not prepared for this geometry");
+        xt = static_cast<int8_t *>(ws->ptr);
+    } else {
+        if (wh) wh->chain_in.valid = false;     // (an ordinary call overwrites a prepared copy)
         int wrc = ws_get(ws, copy_bytes + part_bytes, s, (void **)&xt);
         if (wrc) return wrc;
         int prc = launch_pad(io, x, bits, xt, N, q.Cin, H, W, Ty - 1, Tx - 1, Cp, xmajor, s);
@@ -1055,12 +1060,15 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
     if (part_bytes) c.partial = reinterpret_cast<int32_t *>(xt + copy_bytes);
     if (xmajor) c.dt_wide = ensure_wide(wh, s);
     if (c.dt_wide) { c.wide_digits = wh->dtw_digits; c.wide_c = wh->dtw_c; }
-    if (border && out_elems < 0x7fffffffull) {      // let the product kernel take the border terms off where it can
-        c.zsum = zsum;
+    const bool chained = io && io->chain.buf;
+    if ((border || chained) && out_elems < 0x7fffffffull) {     // the product kernel takes the border terms off where it can; its
+        if (border) c.zsum = zsum;                              // chained copy needs the true output position of a phase's pixel
         c.cv_Ho = Ho; c.cv_Wo = Wo; c.cv_H = H; c.cv_W = W; c.cv_kh = kh; c.cv_kw = kw; c.cv_s = st; c.cv_pad = pad; c.cv_Ly = Ly; c.cv_Lx = Lx;
     }
     bool border_done = false, finished = false;
-    int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io, !border, &border_done, &finished);
+    // a chained copy is written by the wide kernel's epilogue or, for every other kernel, by the pass that rescales afterwards
+    const bool chain_ok_in_kernel = !chained || (xmajor && c.dt_wide && storage == 0 && part_bytes == 0 && out_elems < 0x7fffffffull);
+    int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io, !border && chain_ok_in_kernel, &border_done, &finished);
     rc = ws_put(ws, xt, s, rc);
     if (rc != ADAPT_OK) return rc;
     const size_t planes = (size_t)N * q.N;
@@ -1784,6 +1792,100 @@ int adapt_conv_transpose2d_layer_f32(const adapt_weights *h, const float *x_dev,
             return lines_conv_transpose2d(h->bits, h->storage, q, h->dt_dev, h->zsum_dev, nullptr, out, N, H, W, h->kh, h->kw, h->stride,
                                           pad, s, &h->ws, &io, h);
     }
+    int8_t *q8 = nullptr;
+    if ((rc = quantize_into_ws(h, io, (size_t)N * h->Cin * H * W, s, &q8))) return rc;
+    return convt_rows(h->lut, q8, h->w8_dev, out, N, h->Cin, H, W, h->N, h->kh, h->kw, h->stride, pad, s, h, &io);
+}
+
+// geometry of the phase form of a transposed convolution layer call, or UNSUPPORTED
+static int convt_chain_geo(const adapt_weights *h, int N, int H, int W, int pad, LinesShape *q, long long *Ho, long long *Wo, const char *who) {
+    if (N < 0 || H < 1 || W < 1 || pad < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
+    *Ho = ((long long)H - 1) * h->stride - 2LL * pad + h->kh; *Wo = ((long long)W - 1) * h->stride - 2LL * pad + h->kw;
+    if (*Ho < 1 || *Wo < 1) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: empty output", who);
+    if ((long long)N * h->N * *Ho * *Wo > 0x7fffffffLL || (long long)N * h->Cin * H * W > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
+    if (!(h->phased && convt_phases_ok(H, W, h->kh, h->kw, h->stride, pad)))
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: only geometries that take the phase form (filter a multiple of the stride, more than one input pixel)", who);
+    *q = convt_phase_shape(h->bits, h->N, h->Cin, h->kh, h->kw, h->stride);
+    const long long xt_bytes = (long long)N * (H + 2LL * (q->kh - 1)) * (W + 2LL * (q->kw - 1)) * q->Cp;
+    if (xt_bytes >= 0x7fffff00LL) return fail(ADAPT_ERR_UNSUPPORTED, "%s: input copy of 2 GiB or more", who);
+    return ADAPT_OK;
+}
+
+int adapt_conv_transpose2d_chain_prepare(const adapt_weights *h, int N, int H, int W, int pad, void *stream) {
+    const char *who = "adapt_conv_transpose2d_chain_prepare";
+    int rc = check_weights(h, 2, who);
+    if (rc) return rc;
+    h->chain_in.valid = false;
+    LinesShape q;
+    long long Ho, Wo;
+    if ((rc = convt_chain_geo(h, N, H, W, pad, &q, &Ho, &Wo, who))) return rc;
+    if (N == 0) return ADAPT_OK;
+    // the layout decisions of lines_conv_transpose2d
+    const int st = h->stride, Ty = q.kh, Tx = q.kw;
+    const int Qy = (int)(Ho / st), Qx = (int)(Wo / st), M = N * Qy * Qx;
+    const int xmajor = (lines_rows_per_lane(M, q.n_tiles * st * st, q.Cc, Ty * Tx) == 8 && Qx % 4 == 0 && M % 8 == 0 && q.Cc % 4 == 0) ? 1 : 0;
+    const size_t xt_bytes = (size_t)N * (H + 2 * (Ty - 1)) * (W + 2 * (Tx - 1)) * q.Cp;
+    const size_t copy_bytes = ((xt_bytes + 64 + 255) / 256) * 256;
+    const size_t part_bytes = lines_partial_bytes(M, q.n_tiles * st * st, q.Cc, Ty * Tx, (size_t)N * q.N * Ho * Wo);
+    int8_t *xt = nullptr;
+    if ((rc = ws_get(&h->ws, copy_bytes + part_bytes, (hipStream_t)stream, (void **)&xt))) return rc;
+    adapt::fill_u32_kernel<<<ew_grid(copy_bytes / 4), 256, 0, (hipStream_t)stream>>>(reinterpret_cast<uint32_t *>(xt), 0u, copy_bytes / 4);
+    HIP_TRY(hipGetLastError());
+    auto &ci = h->chain_in;
+    ci.N = N; ci.H = H; ci.W = W; ci.sh = ci.sw = st; ci.ph = Ty - 1; ci.pw = Tx - 1; ci.dh = ci.dw = pad;     // (dh, dw: the layer's padding)
+    ci.xmajor = xmajor; ci.valid = true;
+    return ADAPT_OK;
+}
+
+int adapt_conv_transpose2d_layer_chain_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W, int pad, float s_x,
+                                           float s_out, const float *s_out_vec_dev, const float *bias_dev, int act,
+                                           const adapt_weights *next, float s_next, void *stream) {
+    const char *who = "adapt_conv_transpose2d_layer_chain_f32";
+    int rc = check_weights(h, 2, who);
+    if (rc) return rc;
+    const bool input_ready = x_dev == nullptr;
+    LinesShape q;
+    long long Ho = 0, Wo = 0;
+    const bool phase_form = h->phased && H >= 1 && W >= 1 && pad >= 0 && convt_phases_ok(H, W, h->kh, h->kw, h->stride, pad);
+    if (input_ready || phase_form) {
+        if ((rc = convt_chain_geo(h, N, H, W, pad, &q, &Ho, &Wo, who))) return rc;
+    } else {
+        if (N < 0 || H < 1 || W < 1 || pad < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
+        Ho = ((long long)H - 1) * h->stride - 2LL * pad + h->kh; Wo = ((long long)W - 1) * h->stride - 2LL * pad + h->kw;
+        if (Ho < 1 || Wo < 1) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: empty output", who);
+        if ((long long)N * h->N * Ho * Wo > 0x7fffffffLL || (long long)N * h->Cin * H * W > 0x7fffffffLL)
+            return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
+    }
+    if (N == 0) return ADAPT_OK;
+    if (input_ready) {
+        const auto &ci = h->chain_in;
+        if (!ci.valid || ci.N != N || ci.H != H || ci.W != W || ci.dh != pad || ci.sh != h->stride)
+            return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: x_dev is NULL but the handle was not prepared for this geometry", who);
+    }
+    LayerIO io;
+    if ((rc = layer_io(&io, h, input_ready ? reinterpret_cast<const float *>(y_dev) : x_dev, y_dev, s_x, s_out, s_out_vec_dev, bias_dev, act, who)))
+        return rc;
+    if (input_ready) io.xf = nullptr;
+    if (next) {
+        if (!next || (next->kind != 1 && next->kind != 2)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: next is not a convolution handle", who);
+        if ((rc = check_weights(next, next->kind, who))) return rc;
+        if (next == h) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: a layer cannot chain into itself (one workspace per handle)", who);
+        const auto &ci = next->chain_in;
+        if (!ci.valid || ci.N != N || ci.H != Ho || ci.W != Wo || next->Cin != h->N || !next->ws.ptr)
+            return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: the next layer was not prepared for this layer's output", who);
+        if (!(s_next > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: s_next must be > 0", who);
+        io.chain.buf = static_cast<int8_t *>(next->ws.ptr);
+        io.chain.xmajor = ci.xmajor; io.chain.Hp = ci.H + 2 * ci.ph; io.chain.Wp = ci.W + 2 * ci.pw; io.chain.Cp = next->Cp;
+        io.chain.ph = ci.ph; io.chain.pw = ci.pw;
+        io.chain.scale = s_next; io.chain.Q = (float)((1 << (next->bits - 1)) - 1); io.chain.mask = (1u << next->bits) - 1u;
+        io.chain_wo = (int)Wo;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    int32_t *out = reinterpret_cast<int32_t *>(y_dev);
+    if (input_ready || phase_form)
+        return lines_conv_transpose2d(h->bits, h->storage, q, h->dt_dev, h->zsum_dev, nullptr, out, N, H, W, h->kh, h->kw, h->stride, pad, s,
+                                      &h->ws, &io, h, input_ready);
     int8_t *q8 = nullptr;
     if ((rc = quantize_into_ws(h, io, (size_t)N * h->Cin * H * W, s, &q8))) return rc;
     return convt_rows(h->lut, q8, h->w8_dev, out, N, h->Cin, H, W, h->N, h->kh, h->kw, h->stride, pad, s, h, &io);

@@ -378,11 +378,12 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const Lin
     // (oy, ox + i * out_sx); the taps that lay over the zero border are taken off for the few runs that touch the border
     int oy = 0, ox = 0;
     bool near_border = false;
-    if (EXTRA && p.zsum) {
+    const bool true_pos = EXTRA && p.cv_Wo > 0 && (p.zsum || p.chain.buf);      // (cv_Wo > 0: a transposed convolution)
+    if (true_pos) {
         const int oy0 = out_off / p.cv_Wo, ox0 = out_off - oy0 * p.cv_Wo;       // uniform: once per workgroup
         oy = oy0 + a0 * (p.out_sy / p.cv_Wo);
         ox = ox0 + b0 * p.out_sx;
-        near_border = oy < p.cv_Ly || oy >= p.cv_Ho - p.cv_Ly || ox < p.cv_Lx || ox + 3 * p.out_sx >= p.cv_Wo - p.cv_Lx;
+        if (p.zsum) near_border = oy < p.cv_Ly || oy >= p.cv_Ho - p.cv_Ly || ox < p.cv_Lx || ox + 3 * p.out_sx >= p.cv_Wo - p.cv_Lx;
     }
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -399,7 +400,10 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const Lin
         for (int i = 0; i < 4; ++i) f[i] = p.shift < 0 ? finish_sum<EXTRA>(p, w[i][t], n, (size_t)(q0 + i * sx - outp)) : w[i][t];
         if (EXTRA && p.chain.buf) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) p.chain.put(img, n, a0, b0 + i, __uint_as_float(f[i]));
+            for (int i = 0; i < 4; ++i) {
+                if (true_pos) p.chain.put(img, n, oy, ox + i * p.out_sx, __uint_as_float(f[i]));   // a phase's pixels of the output
+                else p.chain.put(img, n, a0, b0 + i, __uint_as_float(f[i]));
+            }
         }
         if (p.shift < 0 && sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
             *reinterpret_cast<uint4 *>(q0) = make_uint4(f[0], f[1], f[2], f[3]);

@@ -315,7 +315,9 @@ class SeparableConv:
 
 
 class DCGAN:
-    def __init__(self, cfg, device="cuda"):
+    def __init__(self, cfg, device="cuda", chain=True):
+        self.chain = chain
+        self._chain_shape = None
         self.bits = cfg["bits"]
         self.lut = B.Lut(cfg["lut"], self.bits)
         self.plan = cfg["plan"]
@@ -323,11 +325,46 @@ class DCGAN:
         self.pws = [B.adapt_weights_pack_conv_transpose2d(self.lut, qw, s) for (qw, _), (_, _, s, _) in zip(self.qws, self.plan)]
         self.scales = None
 
+    def _forward_chained(self, z):
+        """Frozen scales: every layer writes the next layer's quantised input copy in its epilogue (one kernel per layer
+        after the first).  Returns None when a layer's geometry cannot be prepared (the per-layer calls serve it then)."""
+        n = z.shape[0]
+        nl = len(self.plan)
+        shapes = [tuple(z.shape)]
+        for i, (cin, cout, s, p) in enumerate(self.plan):
+            h, w = shapes[-1][2:]
+            k = self.qws[i][0].shape[2]
+            shapes.append((n, cout, (h - 1) * s - 2 * p + k, (w - 1) * s - 2 * p + k))
+        if self._chain_shape != shapes[0]:
+            try:
+                for i in range(1, nl):
+                    B.adapt_conv_transpose2d_chain_prepare(self.pws[i], n, shapes[i][2], shapes[i][3], self.plan[i][3])
+            except B.AdaptError as e:
+                if e.code != -2:
+                    raise
+                self.chain = False
+                return None
+            self._outs = [torch.empty(shapes[i + 1], dtype=torch.float32, device=z.device) for i in range(nl)]
+            self._chain_shape = shapes[0]
+        x = z
+        for i, (cin, cout, s, p) in enumerate(self.plan):
+            s_x = self.scales[i]
+            nxt = self.pws[i + 1] if i + 1 < nl else None
+            B.adapt_conv_transpose2d_layer_chain_f32(self.pws[i], x if i == 0 else None, s_x, _f(s_x) * _f(self.qws[i][1]), self._outs[i], p,
+                                                     act=B.ACT_TANH if i == nl - 1 else B.ACT_RELU, next_pw=nxt,
+                                                     s_next=self.scales[i + 1] if nxt is not None else 1.0,
+                                                     in_shape=(n, shapes[i][2], shapes[i][3]))
+        return self._outs[-1]
+
     def forward(self, z, keep=None):
         used = []
         x = z
         nl = len(self.plan)
         acc = None
+        if self.chain and self.scales is not None and keep is None:
+            out = self._forward_chained(z)
+            if out is not None:
+                return dict(out=out, scales=list(self.scales), last_acc=None)
         for i, (cin, cout, s, p) in enumerate(self.plan):
             if self.scales is not None and keep is None:        # frozen scales: one fused call per layer
                 s_x = self.scales[i]

@@ -599,8 +599,12 @@ def test_config5_dcgan_full_size(B, bits):
     for i, (g, o) in enumerate(zip(keep, want["accs"])):
         assert (host(g) == o).all(), f"layer {i}"
     assert_f32_close(host(got["out"]), want["out"])
-    again = net.forward(dev(c["z"]))                        # frozen scales: one fused call per layer
+    again = net.forward(dev(c["z"]))                        # frozen scales, layers chained: one kernel per layer after the first
+    assert net.chain and net._chain_shape is not None, "the benchmark shapes must take the chained form"
     assert bits_equal(host(again["out"]), host(got["out"]))
+    plain = gnet.DCGAN(c, chain=False)
+    plain.scales = list(net.scales)
+    assert bits_equal(host(plain.forward(dev(c["z"]))["out"]), host(got["out"]))       # one fused call per layer
 
 
 # ------------------------------------------------------------------ long-matrix ("lines") kernel via packed weights
@@ -1677,6 +1681,86 @@ def test_random_chains_match_oracle(B, seed):
             bad.append(desc)
     assert not bad, bad
     assert ran >= 25
+
+
+CONVT_CHAIN_CASES = [
+    # N, C0, H, W, (C1, k1, s1, p1), consumer ("t" transposed / "c" ordinary, C2, k2, s2, p2), bits
+    (16, 64, 8, 8, (32, 4, 2, 1), ("t", 16, 4, 2, 1), 8),      # wide kernels on both sides, borders taken off in the epilogue
+    (256, 100, 1, 1, (32, 4, 1, 0), ("t", 16, 4, 2, 1), 6),    # single input pixel (a linear layer) into a phase-form layer
+    (4, 8, 5, 6, (12, 3, 2, 0), ("t", 5, 4, 2, 1), 8),         # producer in gather form (3 is no multiple of 2), ragged sizes
+    (3, 7, 5, 5, (9, 2, 2, 0), ("t", 4, 2, 2, 0), 7),          # no border terms at all, generic kernels
+    (8, 32, 8, 8, (32, 4, 2, 1), ("c", 16, 3, 1, 1), 8),       # into an ordinary convolution
+    (32, 128, 16, 16, (64, 4, 2, 1), ("t", 8, 4, 2, 1), 8),    # long layers: several rounds of workgroups
+]
+
+
+@pytest.mark.parametrize("case", CONVT_CHAIN_CASES)
+def test_chained_transposed_convolutions(B, case):
+    """A transposed-convolution layer (ReLU) that writes the next layer's quantised input copy, the next layer run from
+    that copy: both outputs bit-identical to the oracle's layer-by-layer pass; twice, to reuse the prepared buffer."""
+    N, C0, H, W, (C1, k1, s1, p1), (kind2, C2, k2, s2, p2), bits = case
+    rng = np.random.default_rng(sum(case[:4]) + bits + C1 + C2)
+    lut = wl.make_lut(bits)
+    L = B.Lut(lut, bits)
+    th = orc.host_threads()
+    x = rng.standard_normal((N, C0, H, W)).astype(np.float32)
+    w1 = wl.random_i8(rng, (C0, C1, k1, k1), bits, "gauss")
+    s_x = orc.scale_from_amax(orc.absmax(x), bits)
+    acc1 = orc.approx_conv_transpose2d(lut, bits, orc.quantize(x, s_x, bits), w1, s1, p1, threads=th)
+    n_, c_, h1, w1_ = acc1.shape
+    y1 = orc.relu(orc.dequant(acc1, np.float32(s_x) * np.float32(0.02), n_, c_, h1 * w1_)).reshape(acc1.shape)
+    s_y = orc.scale_from_amax(orc.absmax(y1), bits)
+    qy = orc.quantize(y1, s_y, bits)
+    if kind2 == "t":
+        w2 = wl.random_i8(rng, (C1, C2, k2, k2), bits, "gauss")
+        acc2 = orc.approx_conv_transpose2d(lut, bits, qy, w2, s2, p2, threads=th)
+    else:
+        w2 = wl.random_i8(rng, (C2, C1, k2, k2), bits, "gauss")
+        acc2 = orc.approx_conv2d(lut, bits, qy, w2, (s2, s2), (p2, p2), threads=th)
+    y2 = orc.tanh(orc.dequant(acc2, np.float32(s_y) * np.float32(0.01), n_, C2, acc2.shape[2] * acc2.shape[3])).reshape(acc2.shape)
+    pa = B.adapt_weights_pack_conv_transpose2d(L, dev(w1), s1)
+    if kind2 == "t":
+        pb = B.adapt_weights_pack_conv_transpose2d(L, dev(w2), s2)
+        B.adapt_conv_transpose2d_chain_prepare(pb, N, h1, w1_, p2)
+    else:
+        pb = B.adapt_weights_pack_conv2d(L, dev(w2))
+        B.adapt_conv2d_chain_prepare(pb, N, h1, w1_, (s2, s2), (p2, p2))
+    o1 = torch.empty(acc1.shape, dtype=torch.float32, device="cuda")
+    o2 = torch.empty(acc2.shape, dtype=torch.float32, device="cuda")
+    for rep in range(2):
+        B.adapt_conv_transpose2d_layer_chain_f32(pa, dev(x), s_x, np.float32(s_x) * np.float32(0.02), o1, p1, act=B.ACT_RELU, next_pw=pb, s_next=s_y)
+        o2.zero_()
+        if kind2 == "t":
+            B.adapt_conv_transpose2d_layer_chain_f32(pb, None, s_y, np.float32(s_y) * np.float32(0.01), o2, p2, act=B.ACT_TANH, in_shape=(N, h1, w1_))
+        else:
+            B.adapt_conv2d_layer_chain_f32(pb, None, s_y, np.float32(s_y) * np.float32(0.01), o2, (s2, s2), (p2, p2), act=B.ACT_TANH,
+                                           in_shape=(N, h1, w1_))
+        assert bits_equal(host(o1), y1), rep
+        assert bits_equal(host(o2), y2), rep
+
+
+def test_transposed_chain_refusals(B):
+    L = B.Lut(wl.make_lut(8), 8)
+    rng = np.random.default_rng(6)
+    p3 = B.adapt_weights_pack_conv_transpose2d(L, dev(wl.random_i8(rng, (8, 8, 3, 3), 8)), 2)      # 3 is no multiple of 2: no phase form
+    with pytest.raises(B.AdaptError) as e:
+        B.adapt_conv_transpose2d_chain_prepare(p3, 2, 5, 5, 0)
+    assert e.value.code == -2
+    p4 = B.adapt_weights_pack_conv_transpose2d(L, dev(wl.random_i8(rng, (8, 8, 4, 4), 8)), 2)
+    y = torch.empty((2, 8, 10, 10), device="cuda")
+    with pytest.raises(B.AdaptError) as e:      # not prepared
+        B.adapt_conv_transpose2d_layer_chain_f32(p4, None, 1.0, 1.0, y, 1, in_shape=(2, 5, 5))
+    assert e.value.code == -1
+    B.adapt_conv_transpose2d_chain_prepare(p4, 2, 5, 5, 1)
+    with pytest.raises(B.AdaptError) as e:      # prepared for another size
+        B.adapt_conv_transpose2d_layer_chain_f32(p4, None, 1.0, 1.0, y, 1, in_shape=(2, 6, 5))
+    assert e.value.code == -1
+    pa = B.adapt_weights_pack_conv_transpose2d(L, dev(wl.random_i8(rng, (8, 8, 4, 4), 8)), 2)
+    x = torch.zeros((2, 8, 3, 3), device="cuda")
+    y6 = torch.empty((2, 8, 6, 6), device="cuda")
+    with pytest.raises(B.AdaptError) as e:      # the consumer expects 5 x 5 inputs, this layer makes 6 x 6
+        B.adapt_conv_transpose2d_layer_chain_f32(pa, x, 1.0, 1.0, y6, 1, next_pw=p4, s_next=1.0)
+    assert e.value.code == -1
 
 
 def test_chain_refuses_unprepared_handles(B):
