@@ -67,6 +67,21 @@ struct ChainOut {
     }
 };
 
+// Epilogues of the x-major kernels: lane (hq, cq) of a group of 8 lanes (j = 2 cq + hq) holds four consecutive pixels of
+// channel cq (and cq + 4) of its channel tile.  `mine` = its four codes of one of them (byte i = pixel i).  Returned:
+// the codes of pixel cq in the four channels that the lanes (hq, 0..3) of the group hold, byte c = channel c — one
+// aligned word of the next layer's copy instead of four single bytes.  All lanes of the group must call it.
+__device__ __forceinline__ uint32_t chain_gather4(uint32_t mine, int lane, int hq, int cq) {
+    const int base = (lane & ~7) + hq;
+    uint32_t word = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const uint32_t v = (uint32_t)__builtin_amdgcn_ds_bpermute((base + 2 * c) << 2, (int)mine);
+        word |= ((v >> (8 * cq)) & 0xffu) << (8 * c);
+    }
+    return word;
+}
+
 struct LinesParams {
     const int8_t *xt;       // activations (see above)
     const uint4 *dt;        // derived tables [n_tiles][steps][2^b lines][8 columns] x 16 B
@@ -1203,6 +1218,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
         if (r0 + 4 > p.M) return;           // M is a multiple of 8 here
         int img, a0, b0;
         row_pos(r0, img, a0, b0);
+        uint32_t codes[2] = {0u, 0u};       // chained copy: this lane's four codes per channel tile half (byte i = pixel i)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const int n = nt * 8 + (j >> 1) + 4 * t;
@@ -1213,8 +1229,13 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
 #pragma unroll
             for (int i = 0; i < 4; ++i) f[i] = p.shift < 0 ? finish_sum(p, w[i][t], n, (size_t)(q0 + i * sx - outp)) : w[i][t];
             if (p.chain.buf) {
+                if (nt * 8 + 4 * t + 3 < p.N) {     // the whole channel quad exists: exchanged below, stored as words
 #pragma unroll
-                for (int i = 0; i < 4; ++i) p.chain.put(img, n, a0, b0 + i, __uint_as_float(f[i]));
+                    for (int i = 0; i < 4; ++i) codes[t] |= p.chain.code(__uint_as_float(f[i])) << (8 * i);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) p.chain.put(img, n, a0, b0 + i, __uint_as_float(f[i]));
+                }
             }
             if (p.shift < 0 && sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
                 *reinterpret_cast<uint4 *>(q0) = make_uint4(f[0], f[1], f[2], f[3]);
@@ -1224,6 +1245,13 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
                     if (p.shift < 0) q0[i * sx] = (int32_t)f[i];
                     else q0[i * sx] = (int32_t)((uint32_t)q0[i * sx] + (f[i] << p.shift));
                 }
+            }
+        }
+        if (p.chain.buf) {      // the four lanes that hold one pixel run's four channels trade bytes: words instead of bytes
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const uint32_t word = chain_gather4(codes[t], lane, j & 1, j >> 1);
+                if (nt * 8 + 4 * t + 3 < p.N) p.chain.put4(img, nt * 8 + 4 * t, a0, b0 + (j >> 1), word);
             }
         }
     } else {

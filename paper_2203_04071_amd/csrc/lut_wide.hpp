@@ -385,6 +385,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const Lin
         ox = ox0 + b0 * p.out_sx;
         if (p.zsum) near_border = oy < p.cv_Ly || oy >= p.cv_Ho - p.cv_Ly || ox < p.cv_Lx || ox + 3 * p.out_sx >= p.cv_Wo - p.cv_Lx;
     }
+    uint32_t codes[2] = {0u, 0u};           // chained copy: this lane's four codes per channel tile half (byte i = pixel i)
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
         const int n = nt * 8 + 4 * t + cq;
@@ -399,10 +400,15 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const Lin
 #pragma unroll
         for (int i = 0; i < 4; ++i) f[i] = p.shift < 0 ? finish_sum<EXTRA>(p, w[i][t], n, (size_t)(q0 + i * sx - outp)) : w[i][t];
         if (EXTRA && p.chain.buf) {
+            if (nt * 8 + 4 * t + 3 < p.N) {         // the whole channel quad exists: exchanged below, stored as words
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (true_pos) p.chain.put(img, n, oy, ox + i * p.out_sx, __uint_as_float(f[i]));   // a phase's pixels of the output
-                else p.chain.put(img, n, a0, b0 + i, __uint_as_float(f[i]));
+                for (int i = 0; i < 4; ++i) codes[t] |= p.chain.code(__uint_as_float(f[i])) << (8 * i);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (true_pos) p.chain.put(img, n, oy, ox + i * p.out_sx, __uint_as_float(f[i]));   // a phase's pixels of the output
+                    else p.chain.put(img, n, a0, b0 + i, __uint_as_float(f[i]));
+                }
             }
         }
         if (p.shift < 0 && sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
@@ -412,6 +418,16 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_wide_kernel(const Lin
             for (int i = 0; i < 4; ++i) {
                 if (p.shift < 0) q0[i * sx] = (int32_t)f[i];
                 else q0[i * sx] = (int32_t)((uint32_t)q0[i * sx] + (f[i] << p.shift));
+            }
+        }
+    }
+    if (EXTRA && p.chain.buf) {     // the four lanes that hold one pixel run's four channels trade bytes: words instead of bytes
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const uint32_t word = chain_gather4(codes[t], lane, hq, cq);
+            if (nt * 8 + 4 * t + 3 < p.N) {
+                if (true_pos) p.chain.put4(img, nt * 8 + 4 * t, oy, ox + cq * p.out_sx, word);
+                else p.chain.put4(img, nt * 8 + 4 * t, a0, b0 + cq, word);
             }
         }
     }
