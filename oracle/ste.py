@@ -1,0 +1,76 @@
+"""CPU oracle: backward pass of an approximate linear layer under the straight-through estimator.
+
+TEST INFRASTRUCTURE ONLY (see the package header): nothing of the product path imports this file.
+
+What is computed (Sec. III-A, "Retraining": training continues through fake-quantisation modules, with the
+straight-through estimator as the derivative of the quantiser; the forward pass goes through the multiplier table).
+The estimator replaces two derivatives by that of the identity:
+
+* the quantiser x -> s * clamp(rint(x / s), -Q, Q) passes a gradient unchanged where its clamp did not act,
+  |rint(x / s)| <= Q, and passes nothing where it did;
+* the table T[a][w] is differentiated as the exact product a * w that it approximates.
+
+For y[m][n] = sum_k x^[m][k] * w^[n][k] + b[n], with x^ = s_x * q(x) and w^ = s_w * q(w) the fake-quantised operands,
+that gives
+
+    dx[m][k] = inside(x[m][k], s_x) * sum_n dy[m][n] * w^[n][k]
+    dw[n][k] = inside(w[n][k], s_w) * sum_m dy[m][n] * x^[m][k]
+    db[n]    = sum_m dy[m][n]
+
+The quantiser's decisions (code, inside / clipped) are taken in fp32 exactly as the forward quantiser takes them
+(IEEE division, round half to even); a fake-quantised value is one fp32 product code * s; the three sums are formed in
+fp64.  Readings where the paper is silent: "inside" is decided on the rounded code, so the element that defines a
+max-abs scale always keeps its gradient; NaN inputs get no gradient.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def _codes_f32(x, scale):
+    """rint(x / s) in fp32, before the clamp."""
+    x = np.asarray(x, dtype=np.float32)
+    s = np.float32(scale)
+    with np.errstate(invalid="ignore", over="ignore"):
+        return np.rint(x / s).astype(np.float32)
+
+
+def clip_inside(x, scale, bits) -> np.ndarray:
+    """True where the quantiser's clamp did not act on x."""
+    Q = np.float32((1 << (int(bits) - 1)) - 1)
+    r = _codes_f32(x, scale)
+    with np.errstate(invalid="ignore"):
+        return np.abs(r) <= Q              # False for NaN
+
+
+def fake_quant(x, scale, bits) -> np.ndarray:
+    """s * clamp(rint(x / s), -Q, Q) as fp32 (NaN -> 0, like the forward quantiser)."""
+    Q = np.float32((1 << (int(bits) - 1)) - 1)
+    r = _codes_f32(x, scale)
+    r = np.where(np.isnan(r), np.float32(0), r)
+    r = np.minimum(np.maximum(r, -Q), Q).astype(np.float32)
+    return (r * np.float32(scale)).astype(np.float32)
+
+
+def ste_linear_backward(dy, x, w, s_x, s_w, bits):
+    """dy [M][N], x [M][K], w [N][K] (fp32) -> dx [M][K], dw [N][K], db [N] in fp64."""
+    dy = np.asarray(dy, dtype=np.float32)
+    x = np.asarray(x, dtype=np.float32)
+    w = np.asarray(w, dtype=np.float32)
+    M, N = dy.shape
+    assert x.shape[0] == M and w.shape[0] == N and x.shape[1] == w.shape[1]
+    dy64 = dy.astype(np.float64)
+    xh = fake_quant(x, s_x, bits).astype(np.float64)
+    wh = fake_quant(w, s_w, bits).astype(np.float64)
+    dx = (dy64 @ wh) * clip_inside(x, s_x, bits)
+    dw = (dy64.T @ xh) * clip_inside(w, s_w, bits)
+    db = dy64.sum(axis=0)
+    return dx, dw, db
+
+
+def ste_linear_backward_bound(dy, x, w, s_x, s_w, bits):
+    """sum of |terms| of each output: what an fp32 accumulation error is measured against."""
+    dy64 = np.abs(np.asarray(dy, dtype=np.float32).astype(np.float64))
+    xh = np.abs(fake_quant(x, s_x, bits).astype(np.float64))
+    wh = np.abs(fake_quant(w, s_w, bits).astype(np.float64))
+    return dy64 @ wh, dy64.T @ xh, dy64.sum(axis=0)
