@@ -376,6 +376,25 @@ int adapt_approx_conv2d_func_i16(int kind, int param, int bits, const int16_t *x
                                  int32_t *acc_dev, int N, int Cin, int H, int W, int Cout, int kh, int kw,
                                  int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, void *stream);
 
+/* ------------------------------------------------------------------ retraining: backward pass */
+
+/* Backward pass of an approximate linear layer y = s_x s_w (table product of q(x), q(w)) + b under the straight-through
+ * estimator (Sec. III-A, "Retraining": training continues through fake-quantisation modules; the estimator stands in
+ * for the derivative of the quantiser, the forward pass goes through the multiplier table).  The quantiser passes a
+ * gradient where its clamp did not act, |rint(x / s)| <= Q = 2^(bits-1) - 1, decided in fp32 exactly as
+ * adapt_quantize_f32 decides; the table is differentiated as the exact product it approximates:
+ *     dx[m][k] = inside(x[m][k], s_x) * sum_n dy[m][n] * (s_w * q(w)[n][k])
+ *     dw[n][k] = inside(w[n][k], s_w) * sum_m dy[m][n] * (s_x * q(x)[m][k])
+ *     db[n]    = sum_m dy[m][n]
+ * dy_dev [M][N], x_dev [M][K], w_dev [N][K]: fp32 device pointers, row-major, dense, the un-quantised operands of the
+ * forward pass; s_x, s_w: the scales the forward pass quantised them with; 2 <= bits <= 16.  dx_dev [M][K], dw_dev
+ * [N][K], db_dev [N]: device pointers, fully overwritten; any of them may be NULL (not computed); none may alias an
+ * input.  Products and sums are fp32 (matrix instructions for dx / dw, a fixed order for db); NaN inputs get no
+ * gradient.  Asynchronous on `stream`, no allocation.  Errors: ADAPT_ERR_INVALID_ARGUMENT (NULL / misaligned pointer,
+ * negative size, bits, scales), ADAPT_ERR_UNSUPPORTED (M or N above 65535 * 128), ADAPT_ERR_HIP. */
+int adapt_ste_linear_backward_f32(const float *dy_dev, const float *x_dev, const float *w_dev, int M, int K, int N, float s_x,
+                                  float s_w, int bits, float *dx_dev, float *dw_dev, float *db_dev, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

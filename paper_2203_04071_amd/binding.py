@@ -36,6 +36,7 @@ EXPORTS = [
     "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32", "adapt_lstm_cell_q_f32", "adapt_lstm_step_f32", "adapt_gru_step_f32", "adapt_rnn_step_f32", "adapt_gru_cell_f32", "adapt_rnn_cell_f32",
     "adapt_lut16_create", "adapt_lut16_create_from_func", "adapt_lut16_destroy", "adapt_lut16_bits", "adapt_quantize_i16_f32",
     "adapt_approx_linear_i16", "adapt_approx_conv2d_i16", "adapt_approx_linear_func_i16", "adapt_approx_conv2d_func_i16",
+    "adapt_ste_linear_backward_f32",
 ]
 
 
@@ -114,6 +115,7 @@ def load() -> ctypes.CDLL:
     L.adapt_lstm_cell_q_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, vp, f32, i32, i32, i32, vp]
     L.adapt_gru_cell_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, vp, vp, f32, i32, i32, i32, vp]
     L.adapt_rnn_cell_f32.argtypes = [vp, vp, f32, f32, vp, i32, vp, vp, f32, i32, i32, i32, vp]
+    L.adapt_ste_linear_backward_f32.argtypes = [vp, vp, vp, i32, i32, i32, f32, f32, i32, vp, vp, vp, vp]
     for name in EXPORTS:
         if name != "adapt_last_error":
             getattr(L, name).restype = i32
@@ -702,3 +704,17 @@ def adapt_mse_from_histogram(counts, amax, bits, out=None, stream=None):
                                          _stream(stream)))
     return out
 
+
+
+def adapt_ste_linear_backward_f32(dy, x, w, s_x, s_w, bits, want=("dx", "dw", "db"), stream=None):
+    """dy [M][N], x [M][K], w [N][K] fp32 -> (dx, dw, db); entries not named in `want` are None."""
+    M, N = dy.shape
+    K = x.shape[1]
+    assert x.shape == (M, K) and w.shape == (N, K)
+    dx = torch.empty((M, K), dtype=torch.float32, device=dy.device) if "dx" in want else None
+    dw = torch.empty((N, K), dtype=torch.float32, device=dy.device) if "dw" in want else None
+    db = torch.empty((N,), dtype=torch.float32, device=dy.device) if "db" in want else None
+    _chk(load().adapt_ste_linear_backward_f32(_ptr(dy, torch.float32), _ptr(x, torch.float32), _ptr(w, torch.float32), M, K, N,
+                                              float(s_x), float(s_w), int(bits), _ptr(dx, torch.float32), _ptr(dw, torch.float32),
+                                              _ptr(db, torch.float32), _stream(stream)))
+    return dx, dw, db

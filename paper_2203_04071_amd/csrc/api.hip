@@ -15,6 +15,7 @@
 #include "lut_rows.hpp"
 #include "lut_grouped.hpp"
 #include "lut_big.hpp"
+#include "ste_backward.hpp"
 
 namespace {
 
@@ -282,6 +283,52 @@ int adapt_dequant_i32(const int32_t *acc_dev, float *y_dev, size_t outer, size_t
     const int vec = (aligned16(acc_dev) && aligned16(y_dev) && (!bias_dev || inner % 4 == 0)) ? 1 : 0;
     adapt::dequant_kernel<<<ew_grid(n / 4 + 1), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(acc_dev, y_dev, n, channels, inner, scale, bias_dev, vec);
     HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
+int adapt_ste_linear_backward_f32(const float *dy_dev, const float *x_dev, const float *w_dev, int M, int K, int N, float s_x,
+                                  float s_w, int bits, float *dx_dev, float *dw_dev, float *db_dev, void *stream) {
+    const char *who = "adapt_ste_linear_backward_f32";
+    if (M < 0 || K < 0 || N < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: negative size", who);
+    if (bits < 2 || bits > 16) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bits=%d not in [2,16]", who, bits);
+    if (!(s_x > 0.0f) || !(s_w > 0.0f) || s_x > 3.0e38f || s_w > 3.0e38f)
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: scales must be finite and > 0", who);
+    const bool want_dx = dx_dev && M > 0 && K > 0, want_dw = dw_dev && N > 0 && K > 0, want_db = db_dev && N > 0;
+    if ((want_dx || want_dw || want_db) && M > 0 && N > 0 && !dy_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL dy_dev", who);
+    if ((want_dx || want_dw) && ((M > 0 && !x_dev) || (N > 0 && !w_dev))) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL x_dev / w_dev", who);
+    for (const void *q : {(const void *)dy_dev, (const void *)x_dev, (const void *)w_dev, (const void *)dx_dev, (const void *)dw_dev, (const void *)db_dev})
+        if (reinterpret_cast<uintptr_t>(q) & 3u) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: pointer not aligned to 4 bytes", who);
+    if (dx_dev && (dx_dev == x_dev || dx_dev == dy_dev || dx_dev == w_dev) || dw_dev && (dw_dev == w_dev || dw_dev == dy_dev || dw_dev == x_dev))
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: a gradient must not alias an input", who);
+    const long long tiles_m = ((long long)M + adapt::STE_TILE - 1) / adapt::STE_TILE, tiles_n = ((long long)N + adapt::STE_TILE - 1) / adapt::STE_TILE;
+    if (tiles_m > 65535 || tiles_n > 65535) return fail(ADAPT_ERR_UNSUPPORTED, "%s: M and N are limited to %d", who, 65535 * adapt::STE_TILE);
+    hipStream_t s = (hipStream_t)stream;
+    const float Q = (float)((1 << (bits - 1)) - 1);
+    const unsigned tiles_k = (unsigned)((K + adapt::STE_TILE - 1) / adapt::STE_TILE);
+    if (want_dx) {          // dx [M][K] = inside(x) * dy [M][N] . fq(w) [N][K]
+        adapt::SteParams p{};
+        p.a = dy_dev; p.b = w_dev; p.o = x_dev; p.c = dx_dev;
+        p.I = M; p.J = K; p.R = N; p.lda = N;
+        p.sb = s_w; p.so = s_x; p.Q = Q;
+        p.vec_a = (aligned16(dy_dev) && N % 4 == 0) ? 1 : 0;
+        p.vec_b = (aligned16(w_dev) && K % 4 == 0) ? 1 : 0;
+        adapt::ste_gemm_kernel<false><<<dim3(tiles_k, (unsigned)tiles_m), adapt::STE_THREADS, 0, s>>>(p);
+        HIP_TRY(hipGetLastError());
+    }
+    if (want_dw) {          // dw [N][K] = inside(w) * dy^T [N][M] . fq(x) [M][K]
+        adapt::SteParams p{};
+        p.a = dy_dev; p.b = x_dev; p.o = w_dev; p.c = dw_dev;
+        p.I = N; p.J = K; p.R = M; p.lda = N;
+        p.sb = s_x; p.so = s_w; p.Q = Q;
+        p.vec_a = (aligned16(dy_dev) && N % 4 == 0) ? 1 : 0;
+        p.vec_b = (aligned16(x_dev) && K % 4 == 0) ? 1 : 0;
+        adapt::ste_gemm_kernel<true><<<dim3(tiles_k, (unsigned)tiles_n), adapt::STE_THREADS, 0, s>>>(p);
+        HIP_TRY(hipGetLastError());
+    }
+    if (want_db) {
+        adapt::ste_colsum_kernel<<<(unsigned)((N + 31) / 32), adapt::STE_THREADS, 0, s>>>(dy_dev, db_dev, M, N);
+        HIP_TRY(hipGetLastError());
+    }
     return ADAPT_OK;
 }
 

@@ -1,0 +1,132 @@
+"""GPU parity of the straight-through backward pass (Sec. III-A, "Retraining") against the CPU oracle, through the C ABI.
+
+Tolerance.  The library forms every gradient element as an fp32 sum of R products of fp32 operands (matrix
+instructions; any order).  For any order of an fp32 dot product of length R the error is at most
+gamma(R + 1) * sum |a| |b| with gamma(n) = n u / (1 - n u), u = 2^-24; the oracle's fp64 sum is exact to 1e-16 of the
+same quantity.  The clip mask and the fake-quantised operand values are decided in fp32 on both sides, so they
+agree exactly: a masked element must be exactly 0.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ste
+
+pytestmark = pytest.mark.gpu
+
+U = 2.0 ** -24
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2203_04071_amd import binding
+    binding.load()
+    assert torch.cuda.is_available()
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def make(M, K, N, bits, seed, clip=1.0):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    w = (rng.standard_normal((N, K)) * 0.1).astype(np.float32)
+    dy = rng.standard_normal((M, N)).astype(np.float32)
+    Q = (1 << (bits - 1)) - 1
+    # scales from a clipping point below the maximum (as a percentile calibrator gives): some elements are clipped
+    s_x = np.float32(clip * (np.abs(x).max() if x.size else 1.0) / Q)
+    s_w = np.float32(clip * (np.abs(w).max() if w.size else 1.0) / Q)
+    return dy, x, w, s_x, s_w
+
+
+def check(got, want, bound, R):
+    got = got.detach().cpu().numpy().astype(np.float64)
+    assert got.shape == want.shape
+    g = (R + 1) * U / (1 - (R + 1) * U)
+    err = np.abs(got - want)
+    assert (err <= g * bound + 1e-37).all(), f"max err/bound = {np.max(err / (g * bound + 1e-37))}"
+    assert (got[want == 0] == 0).all()
+
+
+CASES = [(1, 1, 1), (3, 5, 2), (64, 256, 128), (130, 129, 131), (257, 40, 300), (128, 128, 128), (300, 260, 17), (17, 1000, 33),
+         (512, 16, 1), (1, 300, 513)]
+
+
+@pytest.mark.parametrize("bits,clip", [(8, 0.6), (4, 1.0), (12, 0.8)])
+@pytest.mark.parametrize("M,K,N", CASES)
+def test_ste_linear_backward_matches_oracle(B, M, K, N, bits, clip):
+    dy, x, w, s_x, s_w = make(M, K, N, bits, M * 7 + K * 3 + N + bits, clip)
+    if M * K > 4:
+        x.flat[3] = np.nan                      # no gradient there; its fake-quantised value is 0
+    dx, dw, db = B.adapt_ste_linear_backward_f32(dev(dy), dev(x), dev(w), s_x, s_w, bits)
+    torch.cuda.synchronize()
+    ox, ow, ob = ste.ste_linear_backward(dy, x, w, s_x, s_w, bits)
+    bx, bw, bb = ste.ste_linear_backward_bound(dy, x, w, s_x, s_w, bits)
+    if clip < 1.0 and M * K > 100:
+        assert (ox == 0).sum() > 0 and (ow == 0).sum() > 0          # the mask is exercised
+    check(dx, ox, bx, N)
+    check(dw, ow, bw, M)
+    check(db, ob, bb, M)
+
+
+@pytest.mark.parametrize("M,K,N", [(0, 5, 3), (4, 0, 3), (4, 5, 0), (0, 0, 0)])
+def test_ste_empty_dimensions(B, M, K, N):
+    dy, x, w, s_x, s_w = make(M, K, N, 8, 1)
+    dx, dw, db = B.adapt_ste_linear_backward_f32(dev(dy), dev(x), dev(w), 0.01, 0.01, 8)
+    torch.cuda.synchronize()
+    ox, ow, ob = ste.ste_linear_backward(dy, x, w, 0.01, 0.01, 8)
+    np.testing.assert_array_equal(dx.cpu().numpy(), ox)
+    np.testing.assert_array_equal(dw.cpu().numpy(), ow)             # M = 0: zeros, written
+    check(db, ob, ste.ste_linear_backward_bound(dy, x, w, 0.01, 0.01, 8)[2], M)
+
+
+def test_ste_unaligned_views_and_partial_outputs(B):
+    # buffers that start 4 bytes past a 16-byte boundary take the element-wise loads; outputs left out are not touched
+    M, K, N, bits = 70, 36, 44, 8
+    dy, x, w, s_x, s_w = make(M, K, N, bits, 9, 0.7)
+    def shifted(a):
+        buf = torch.zeros(a.size + 1, dtype=torch.float32, device="cuda")
+        buf[1:] = torch.from_numpy(a.ravel()).cuda()
+        return buf[1:].view(a.shape)
+    ox, ow, ob = ste.ste_linear_backward(dy, x, w, s_x, s_w, bits)
+    bx, bw, bb = ste.ste_linear_backward_bound(dy, x, w, s_x, s_w, bits)
+    dx, dw, db = B.adapt_ste_linear_backward_f32(shifted(dy), shifted(x), shifted(w), s_x, s_w, bits)
+    torch.cuda.synchronize()
+    check(dx, ox, bx, N); check(dw, ow, bw, M); check(db, ob, bb, M)
+    dx, dw, db = B.adapt_ste_linear_backward_f32(dev(dy), dev(x), dev(w), s_x, s_w, bits, want=("dw",))
+    assert dx is None and db is None
+    check(dw, ow, bw, M)
+
+
+def test_ste_full_size_projection_layer(B):
+    # the input projection of the recurrent configuration: 6400 x 512 -> 2048, 7-bit operands, whole result compared
+    M, K, N, bits = 6400, 512, 2048, 7
+    dy, x, w, s_x, s_w = make(M, K, N, bits, 4, 0.5)
+    dx, dw, db = B.adapt_ste_linear_backward_f32(dev(dy), dev(x), dev(w), s_x, s_w, bits)
+    torch.cuda.synchronize()
+    ox, ow, ob = ste.ste_linear_backward(dy, x, w, s_x, s_w, bits)
+    bx, bw, bb = ste.ste_linear_backward_bound(dy, x, w, s_x, s_w, bits)
+    check(dx, ox, bx, N); check(dw, ow, bw, M); check(db, ob, bb, M)
+    # far inside the worst-case bound in practice: the typical error of an fp32 sum grows like sqrt(R)
+    rel = np.abs(dx.cpu().numpy() - ox).max() / np.abs(ox).max()
+    assert rel < 64 * U * np.sqrt(N)
+
+
+def test_ste_refusals(B):
+    dy, x, w, s_x, s_w = make(4, 8, 4, 8, 2)
+    d = [dev(dy), dev(x), dev(w)]
+    for kw in (dict(bits=1), dict(bits=17), dict(s_x=0.0), dict(s_w=float("nan")), dict(s_x=float("inf"))):
+        a = dict(s_x=s_x, s_w=s_w, bits=8); a.update(kw)
+        with pytest.raises(B.AdaptError) as e:
+            B.adapt_ste_linear_backward_f32(d[0], d[1], d[2], a["s_x"], a["s_w"], a["bits"])
+        assert e.value.code == -1
+    L = B.load()
+    import ctypes
+    rc = L.adapt_ste_linear_backward_f32(d[0].data_ptr(), d[1].data_ptr(), d[2].data_ptr(), 4, 8, 4, ctypes.c_float(s_x), ctypes.c_float(s_w), 8,
+                                         d[1].data_ptr(), None, None, None)           # dx aliases x
+    assert rc == -1
+    rc = L.adapt_ste_linear_backward_f32(None, d[1].data_ptr(), d[2].data_ptr(), 4, 8, 4, ctypes.c_float(s_x), ctypes.c_float(s_w), 8,
+                                         None, d[0].data_ptr(), None, None)           # dy missing
+    assert rc == -1
