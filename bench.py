@@ -176,6 +176,21 @@ def build_step(cfg_id, bits, torch, B, gnet, wl, eager=False):
         name = ("extra: approx_conv2d 3x3 s1 p1, batch 32, 64->64 ch, 32x32, 12-bit " +
                 ("table in device memory" if cfg_id == 8 else "Mitchell multiplier as a function"))
         return step, core, wl.lut_macs_conv2d(32, 64, 32, 32, 64, 3, 3, 1, 1, 1, 1), name, L
+    if cfg_id == 10:    # retraining (Sec. III-A): straight-through backward pass of the recurrent configuration's input projection
+        M, K, N = 6400, 512, 2048
+        rng = np.random.default_rng(1234 + 10)
+        x = dev(rng.standard_normal((M, K)).astype(np.float32))
+        w = dev((rng.standard_normal((N, K)) * 0.1).astype(np.float32))
+        dy = dev(rng.standard_normal((M, N)).astype(np.float32))
+        s_x = gnet.calibrated_scale(x, 7)
+        s_w = gnet.calibrated_scale(w, 7)
+        outs = [torch.empty((M, K), dtype=torch.float32, device="cuda"), torch.empty((N, K), dtype=torch.float32, device="cuda"),
+                torch.empty((N,), dtype=torch.float32, device="cuda")]
+
+        def core():
+            B.adapt_ste_linear_backward_f32(dy, x, w, s_x, s_w, 7, out=outs)
+        name = "extra: straight-through backward pass of a linear layer, 6400 x 512 -> 2048, 7-bit operands (dx, dw, db)"
+        return core, core, 2 * M * K * N, name, outs
     raise SystemExit(f"unknown config {cfg_id}")
 
 
@@ -248,6 +263,20 @@ def cpu_baseline(cfg_id, bits, wl):
         dt = time.perf_counter() - t0
         return dict(value=wl.lut_macs_conv2d(8, 64, 32, 32, 64, 3, 3, 1, 1, 1, 1) / dt, unit="LUT-MAC/s", cores=th, kind="oracle",
                     sample="8 of 32 images, one pass")
+    if cfg_id == 10:
+        from oracle import ste
+        M, K, N = 1600, 512, 2048
+        rng = np.random.default_rng(1234 + 10)
+        x = rng.standard_normal((M, K)).astype(np.float32)
+        w = (rng.standard_normal((N, K)) * 0.1).astype(np.float32)
+        dy = rng.standard_normal((M, N)).astype(np.float32)
+        s_x = orc.scale_from_amax(orc.absmax(x), 7)
+        s_w = orc.scale_from_amax(orc.absmax(w), 7)
+        t0 = time.perf_counter()
+        ste.ste_linear_backward(dy, x, w, s_x, s_w, 7)
+        dt = time.perf_counter() - t0
+        return dict(value=4.0 * M * K * N / dt, unit="FLOP/s", cores=th, kind="oracle",
+                    sample="1600 of 6400 rows, one pass (fp64; its two matrix products are numpy's)")
     c = wl.config5(bits=bits, batch=32)
     t0 = time.perf_counter()
     onet.dcgan(c, threads=th)
@@ -261,7 +290,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, help="1-5: the baseline configurations (default 2, the one the metric is quoted on); "
-                    "6: separable convolution block, 7: GRU layer, 8 / 9: the layer of 2 with 12-bit operands, table / function form "
+                    "6: separable convolution block, 7: GRU layer, 8 / 9: the layer of 2 with 12-bit operands, table / function form, "
+                    "10: straight-through backward pass of a linear layer "
                     "(rows beyond the baseline, not bench lines of record)")
     ap.add_argument("--bits", type=int, default=8, help="table bits for config 5 (6 or 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -365,6 +395,11 @@ def main():
             roof.update(bound="l1-gather", peak=gpeak / 1e12, frac=achieved / gpeak,
                         peak_model=f"{cus} CUs x {GATHER_LANES_PER_CLK_PER_CU} gathered lanes/clk x {MODEL_CLOCK_GHZ} GHz; "
                                    "1 lookup (4 B from device memory) per LUT-MAC")
+        if args.config == 10:
+            # two dense fp32 contractions (macs counts the multiply-adds of both): the matrix pipe's fp32 rate
+            roof = dict(bound="mfma", achieved=2 * achieved / 1e12, peak=157.3, unit="TFLOP/s", frac=2 * achieved / 157.3e12, traffic=None,
+                        kernel_ms_avg=k_avg, kernel_ms_min=float(kms.min()), covers="both product kernels and the bias-gradient kernel of the call",
+                        peak_model="published dense fp32 matrix rate of MI355X")
         if args.config == 9:
             # the multiplier as a function: vector integer operations, 64 lanes per clock per compute unit
             apeak = cus * 64 * MODEL_CLOCK_GHZ * 1e9 / MITCHELL_OPS_PER_MAC
@@ -377,15 +412,17 @@ def main():
                     traffic=traffic, note="whole network step (all kernels) against the LDS lookup peak")
 
     out = {
-        "metric": "approximate MACs/sec (LUT-MAC/s), whole step: quantise + table-lookup layer(s) + dequantise",
-        "value": macs / (ms_per_step * 1e-3),
-        "unit": "LUT-MAC/s",
+        "metric": ("approximate MACs/sec (LUT-MAC/s), whole step: quantise + table-lookup layer(s) + dequantise" if args.config != 10 else
+                   "fp32 FLOP/s of the two gradient contractions (fake quantisation and clip masks included in the time)"),
+        "value": macs / (ms_per_step * 1e-3) * (2 if args.config == 10 else 1),
+        "unit": "LUT-MAC/s" if args.config != 10 else "FLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": ("int8 operands, int16 table, int32 accumulate, fp32 scale" if args.config < 8 else
+                  "f32" if args.config == 10 else
                   "int16 operands (12-bit), int32 table or function, int32 accumulate, fp32 scale"),
         "data": "synthetic (seeded)", "prewarm_ms": args.prewarm_ms,
-        "config": {"workload": name, "lut_macs_per_step": macs},
+        "config": {"workload": name, ("lut_macs_per_step" if args.config != 10 else "multiply_adds_per_step"): macs},
         "roofline": roof,
     }
     if not args.no_cpu_baseline:

@@ -706,14 +706,19 @@ def adapt_mse_from_histogram(counts, amax, bits, out=None, stream=None):
 
 
 
-def adapt_ste_linear_backward_f32(dy, x, w, s_x, s_w, bits, want=("dx", "dw", "db"), stream=None):
-    """dy [M][N], x [M][K], w [N][K] fp32 -> (dx, dw, db); entries not named in `want` are None."""
+def adapt_ste_linear_backward_f32(dy, x, w, s_x, s_w, bits, want=("dx", "dw", "db"), out=None, stream=None):
+    """dy [M][N], x [M][K], w [N][K] fp32 -> (dx, dw, db); entries not named in `want` are None.
+    out: (dx, dw, db) tensors to write into (None entries are not computed) instead of new ones."""
     M, N = dy.shape
     K = x.shape[1]
     assert x.shape == (M, K) and w.shape == (N, K)
-    dx = torch.empty((M, K), dtype=torch.float32, device=dy.device) if "dx" in want else None
-    dw = torch.empty((N, K), dtype=torch.float32, device=dy.device) if "dw" in want else None
-    db = torch.empty((N,), dtype=torch.float32, device=dy.device) if "db" in want else None
+    if out is not None:
+        dx, dw, db = out
+        assert (dx is None or dx.shape == (M, K)) and (dw is None or dw.shape == (N, K)) and (db is None or db.shape == (N,))
+    else:
+        dx = torch.empty((M, K), dtype=torch.float32, device=dy.device) if "dx" in want else None
+        dw = torch.empty((N, K), dtype=torch.float32, device=dy.device) if "dw" in want else None
+        db = torch.empty((N,), dtype=torch.float32, device=dy.device) if "db" in want else None
     _chk(load().adapt_ste_linear_backward_f32(_ptr(dy, torch.float32), _ptr(x, torch.float32), _ptr(w, torch.float32), M, K, N,
                                               float(s_x), float(s_w), int(bits), _ptr(dx, torch.float32), _ptr(dw, torch.float32),
                                               _ptr(db, torch.float32), _stream(stream)))

@@ -39,6 +39,34 @@ int fail(int code, const char *fmt, ...) {
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Shape of the gradient products' launch: 128 x 128 outputs per workgroup where that still occupies three quarters of
+// the compute units, else 64 x 64; eight waves per workgroup instead of four (KS = 2) where there are fewer than two
+// workgroups per compute unit.  Env ADAPT_STE_TILE = 64 / 128 and ADAPT_STE_KS = 1 / 2 force one (for measurements).
+// `full`: whole tiles, 16-byte rows.
+int ste_env(const char *name) {
+    const char *e = getenv(name);
+    return e ? atoi(e) : 0;
+}
+void launch_ste_gemm(const adapt::SteParams &p, bool a_t, bool aligned, hipStream_t s) {
+    static const int env_tile = ste_env("ADAPT_STE_TILE"), env_ks = ste_env("ADAPT_STE_KS");
+    const int cus = 256;
+    const long long t128 = (((long long)p.I + 127) / 128) * (((long long)p.J + 127) / 128);
+    int tile = 4 * t128 >= 3 * cus ? 128 : 64;
+    if (env_tile == 64 || env_tile == 128) tile = env_tile;
+    const dim3 grid((unsigned)((p.J + tile - 1) / tile), (unsigned)((p.I + tile - 1) / tile));
+    int ks = (long long)grid.x * grid.y < 2 * cus ? 2 : 1;
+    if (env_ks == 1 || env_ks == 2) ks = env_ks;
+    const bool full = aligned && p.I % tile == 0 && p.J % tile == 0 && p.R % adapt::STE_TR == 0 && p.lda % 4 == 0 && p.R > 0;
+#define STE_LAUNCH4(AT, T, F) \
+    do { if (ks == 2) adapt::ste_gemm_kernel<AT, T, F, 2><<<grid, adapt::STE_THREADS * 2, 0, s>>>(p); \
+         else adapt::ste_gemm_kernel<AT, T, F, 1><<<grid, adapt::STE_THREADS, 0, s>>>(p); } while (0)
+#define STE_LAUNCH2(AT, T) do { if (full) STE_LAUNCH4(AT, T, true); else STE_LAUNCH4(AT, T, false); } while (0)
+    if (a_t) { if (tile == 128) STE_LAUNCH2(true, 128); else STE_LAUNCH2(true, 64); }
+    else { if (tile == 128) STE_LAUNCH2(false, 128); else STE_LAUNCH2(false, 64); }
+#undef STE_LAUNCH2
+#undef STE_LAUNCH4
+}
+
 inline unsigned ew_grid(size_t work_items) {
     size_t g = (work_items + adapt::EW_THREADS - 1) / adapt::EW_THREADS;
     if (g < 1) g = 1;
@@ -300,19 +328,16 @@ int adapt_ste_linear_backward_f32(const float *dy_dev, const float *x_dev, const
         if (reinterpret_cast<uintptr_t>(q) & 3u) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: pointer not aligned to 4 bytes", who);
     if (dx_dev && (dx_dev == x_dev || dx_dev == dy_dev || dx_dev == w_dev) || dw_dev && (dw_dev == w_dev || dw_dev == dy_dev || dw_dev == x_dev))
         return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: a gradient must not alias an input", who);
-    const long long tiles_m = ((long long)M + adapt::STE_TILE - 1) / adapt::STE_TILE, tiles_n = ((long long)N + adapt::STE_TILE - 1) / adapt::STE_TILE;
-    if (tiles_m > 65535 || tiles_n > 65535) return fail(ADAPT_ERR_UNSUPPORTED, "%s: M and N are limited to %d", who, 65535 * adapt::STE_TILE);
+    if (((long long)M + 63) / 64 > 65535 || ((long long)N + 63) / 64 > 65535)
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: M and N are limited to %d", who, 65535 * 64);
     hipStream_t s = (hipStream_t)stream;
     const float Q = (float)((1 << (bits - 1)) - 1);
-    const unsigned tiles_k = (unsigned)((K + adapt::STE_TILE - 1) / adapt::STE_TILE);
     if (want_dx) {          // dx [M][K] = inside(x) * dy [M][N] . fq(w) [N][K]
         adapt::SteParams p{};
         p.a = dy_dev; p.b = w_dev; p.o = x_dev; p.c = dx_dev;
         p.I = M; p.J = K; p.R = N; p.lda = N;
         p.sb = s_w; p.so = s_x; p.Q = Q;
-        p.vec_a = (aligned16(dy_dev) && N % 4 == 0) ? 1 : 0;
-        p.vec_b = (aligned16(w_dev) && K % 4 == 0) ? 1 : 0;
-        adapt::ste_gemm_kernel<false><<<dim3(tiles_k, (unsigned)tiles_m), adapt::STE_THREADS, 0, s>>>(p);
+        launch_ste_gemm(p, false, aligned16(dy_dev) && aligned16(w_dev), s);
         HIP_TRY(hipGetLastError());
     }
     if (want_dw) {          // dw [N][K] = inside(w) * dy^T [N][M] . fq(x) [M][K]
@@ -320,13 +345,11 @@ int adapt_ste_linear_backward_f32(const float *dy_dev, const float *x_dev, const
         p.a = dy_dev; p.b = x_dev; p.o = w_dev; p.c = dw_dev;
         p.I = N; p.J = K; p.R = M; p.lda = N;
         p.sb = s_x; p.so = s_w; p.Q = Q;
-        p.vec_a = (aligned16(dy_dev) && N % 4 == 0) ? 1 : 0;
-        p.vec_b = (aligned16(x_dev) && K % 4 == 0) ? 1 : 0;
-        adapt::ste_gemm_kernel<true><<<dim3(tiles_k, (unsigned)tiles_n), adapt::STE_THREADS, 0, s>>>(p);
+        launch_ste_gemm(p, true, aligned16(dy_dev) && aligned16(x_dev), s);
         HIP_TRY(hipGetLastError());
     }
     if (want_db) {
-        adapt::ste_colsum_kernel<<<(unsigned)((N + 31) / 32), adapt::STE_THREADS, 0, s>>>(dy_dev, db_dev, M, N);
+        adapt::ste_colsum_kernel<<<(unsigned)((N + 31) / 32), adapt::STE_COLSUM_THREADS, 0, s>>>(dy_dev, db_dev, M, N);
         HIP_TRY(hipGetLastError());
     }
     return ADAPT_OK;

@@ -17,10 +17,8 @@ namespace adapt {
 
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
-constexpr int STE_TILE = 128;       // output tile of a workgroup: 128 x 128, one 64 x 64 quarter per wave
-constexpr int STE_TR = 16;          // contraction indices per staged chunk
-constexpr int STE_LD = 132;         // LDS row length in floats (16-byte rows, shifted by 4 banks per row)
-constexpr int STE_THREADS = 256;
+constexpr int STE_TR = 32;          // contraction indices per staged chunk
+constexpr int STE_THREADS = 256;    // four waves, 2 x 2 over the workgroup's output tile (x KS, see the kernel)
 
 // c[i][j] = inside(o[i][j]) * sum_r A(i, r) * fq(b[r][j])
 struct SteParams {
@@ -30,7 +28,6 @@ struct SteParams {
     float *c;           // [I][J]
     int I, J, R, lda;
     float sb, so, Q;
-    int vec_a, vec_b;   // 16-byte loads allowed (aligned base, row length a multiple of 4)
 };
 
 __device__ __forceinline__ float ste_fake_quant(float x, float s, float Q) {
@@ -43,126 +40,189 @@ __device__ __forceinline__ float ste_fake_quant(float x, float s, float Q) {
 
 __device__ __forceinline__ bool ste_inside(float x, float s, float Q) { return fabsf(rintf(x / s)) <= Q; }     // NaN: false
 
-// four consecutive elements of a row-major matrix, zero outside it (col is a multiple of 4)
-__device__ __forceinline__ float4 ste_load4(const float *__restrict__ base, int row, int col, int rows, int cols, int ld, int vec) {
-    float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    if (row < rows && col < cols) {
-        const float *q = base + (size_t)row * (size_t)ld + (size_t)col;
-        if (vec && col + 3 < cols) {
-            v = *reinterpret_cast<const float4 *>(q);
-        } else {
-            v.x = q[0];
-            if (col + 1 < cols) v.y = q[1];
-            if (col + 2 < cols) v.z = q[2];
-            if (col + 3 < cols) v.w = q[3];
-        }
-    }
+// Four consecutive elements of a row-major matrix (col a multiple of 4).  FULL: the whole tile lies inside the matrix
+// and rows are 16-byte aligned, one load.  Otherwise: zero outside the matrix, read without a branch from clamped
+// addresses (rows, cols >= 1), so that the loads of a chunk stay in flight together.
+template <bool FULL>
+__device__ __forceinline__ float4 ste_load4(const float *__restrict__ base, int row, int col, int rows, int cols, int ld) {
+    if (FULL) return *reinterpret_cast<const float4 *>(base + (size_t)row * (size_t)ld + (size_t)col);
+    const float *q = base + (size_t)min(row, rows - 1) * (size_t)ld;
+    const bool in_row = row < rows;
+    float4 v;
+    v.x = q[min(col + 0, cols - 1)];
+    v.y = q[min(col + 1, cols - 1)];
+    v.z = q[min(col + 2, cols - 1)];
+    v.w = q[min(col + 3, cols - 1)];
+    v.x = (in_row && col + 0 < cols) ? v.x : 0.0f;
+    v.y = (in_row && col + 1 < cols) ? v.y : 0.0f;
+    v.z = (in_row && col + 2 < cols) ? v.z : 0.0f;
+    v.w = (in_row && col + 3 < cols) ? v.w : 0.0f;
     return v;
 }
 
-template <bool A_T>
-__global__ __launch_bounds__(STE_THREADS) void ste_gemm_kernel(SteParams p) {
-    __shared__ __align__(16) float As[STE_TR][STE_LD];      // [r][i]
-    __shared__ __align__(16) float Bs[STE_TR][STE_LD];      // [r][j]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int i0 = blockIdx.y * STE_TILE, j0 = blockIdx.x * STE_TILE;
-    const int wi = (wave & 1) * 64, wj = (wave >> 1) * 64;
+// TILE x TILE outputs per workgroup (128: four 32 x 32 blocks per wave; 64: one), FULL as above.  Chunks of 32
+// contraction indices alternate between two LDS buffers: while the matrix pipe works on one, the next chunk's global
+// loads are in flight and are fake-quantised into the other; one barrier per chunk.
+// KS = 2: eight waves; waves w and w + 4 share an output quarter and take alternate pairs of contraction indices, their
+// sums are added through LDS at the end (a fixed order).  For launches with about one workgroup per compute unit:
+// two waves per SIMD, so that one wave's staging arithmetic runs under the other's matrix instructions.
+template <bool A_T, int TILE, bool FULL, int KS>
+__global__ __launch_bounds__(STE_THREADS * KS) void ste_gemm_kernel(SteParams p) {
+    constexpr int THREADS = STE_THREADS * KS;
+    constexpr int LDB = TILE + 4;                   // LDS row length in floats: 16-byte rows, shifted by 4 banks per row
+    constexpr int LDA = A_T ? TILE + 4 : TILE + 1;  // written element by element when the tile arrives transposed
+    constexpr int PASSES = TILE * STE_TR / 4 / THREADS;     // staging passes of THREADS x 4 floats over a 32 x TILE chunk
+    constexpr int TPR = TILE / 4;                   // threads per staged row
+    constexpr int RPP = THREADS / TPR;              // rows per pass
+    constexpr int IPP = THREADS / 8;                // rows of a transposed tile per pass
+    constexpr int WT = TILE / 2, NB = WT / 32;
+    __shared__ __align__(16) float As[2][STE_TR][LDA];      // [r][i]
+    __shared__ __align__(16) float Bs[2][STE_TR][LDB];      // [r][j]
+    const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, kh = tid >> 8;
+    const int i0 = blockIdx.y * TILE, j0 = blockIdx.x * TILE;
+    const int wi = (wave & 1) * WT, wj = (wave >> 1) * WT;
 
-    f32x16_t acc[2][2];
+    f32x16_t acc[NB][NB];
 #pragma unroll
-    for (int bi = 0; bi < 2; ++bi)
+    for (int bi = 0; bi < NB; ++bi)
 #pragma unroll
-        for (int bj = 0; bj < 2; ++bj)
+        for (int bj = 0; bj < NB; ++bj)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[bi][bj][v] = 0.0f;
 
-    float4 ra[2], rb[2];
+    float4 ra[PASSES], rb[PASSES];
     auto fetch = [&](int r0) {
 #pragma unroll
-        for (int pass = 0; pass < 2; ++pass) {
-            const int r = (tid >> 5) + 8 * pass, c4 = (tid & 31) * 4;
-            rb[pass] = ste_load4(p.b, r0 + r, j0 + c4, p.R, p.J, p.J, p.vec_b);
+        for (int pass = 0; pass < PASSES; ++pass) {
+            const int r = tid / TPR + RPP * pass, c4 = (tid % TPR) * 4;
+            rb[pass] = ste_load4<FULL>(p.b, r0 + r, j0 + c4, p.R, p.J, p.J);
             if (A_T) {
-                ra[pass] = ste_load4(p.a, r0 + r, i0 + c4, p.R, p.I, p.lda, p.vec_a);
+                ra[pass] = ste_load4<FULL>(p.a, r0 + r, i0 + c4, p.R, p.I, p.lda);
             } else {
-                const int i = (tid >> 2) + 64 * pass, r4 = (tid & 3) * 4;
-                ra[pass] = ste_load4(p.a, i0 + i, r0 + r4, p.I, p.R, p.lda, p.vec_a);
+                const int i = (tid >> 3) + IPP * pass, r4 = (tid & 7) * 4;
+                ra[pass] = ste_load4<FULL>(p.a, i0 + i, r0 + r4, p.I, p.R, p.lda);
             }
         }
     };
-    auto stash = [&]() {
+    auto stash = [&](int buf) {
 #pragma unroll
-        for (int pass = 0; pass < 2; ++pass) {
-            const int r = (tid >> 5) + 8 * pass, c4 = (tid & 31) * 4;
+        for (int pass = 0; pass < PASSES; ++pass) {
+            const int r = tid / TPR + RPP * pass, c4 = (tid % TPR) * 4;
             float4 q;
             q.x = ste_fake_quant(rb[pass].x, p.sb, p.Q);
             q.y = ste_fake_quant(rb[pass].y, p.sb, p.Q);
             q.z = ste_fake_quant(rb[pass].z, p.sb, p.Q);
             q.w = ste_fake_quant(rb[pass].w, p.sb, p.Q);
-            *reinterpret_cast<float4 *>(&Bs[r][c4]) = q;
+            *reinterpret_cast<float4 *>(&Bs[buf][r][c4]) = q;
             if (A_T) {
-                *reinterpret_cast<float4 *>(&As[r][c4]) = ra[pass];
+                *reinterpret_cast<float4 *>(&As[buf][r][c4]) = ra[pass];
             } else {                                        // the tile arrives with r contiguous: transposed on the way in
-                const int i = (tid >> 2) + 64 * pass, r4 = (tid & 3) * 4;
-                As[r4 + 0][i] = ra[pass].x;
-                As[r4 + 1][i] = ra[pass].y;
-                As[r4 + 2][i] = ra[pass].z;
-                As[r4 + 3][i] = ra[pass].w;
+                const int i = (tid >> 3) + IPP * pass, r4 = (tid & 7) * 4;
+                As[buf][r4 + 0][i] = ra[pass].x;
+                As[buf][r4 + 1][i] = ra[pass].y;
+                As[buf][r4 + 2][i] = ra[pass].z;
+                As[buf][r4 + 3][i] = ra[pass].w;
             }
         }
     };
 
-    fetch(0);
-    for (int r0 = 0; r0 < p.R; r0 += STE_TR) {
-        __syncthreads();                    // every wave has finished reading the previous chunk
-        stash();
-        __syncthreads();
-        if (r0 + STE_TR < p.R) fetch(r0 + STE_TR);          // in flight while this chunk is multiplied
+    const int chunks = (p.R + STE_TR - 1) / STE_TR;
+    if (chunks > 0) { fetch(0); stash(0); }
+    __syncthreads();
+    for (int ch = 0; ch < chunks; ++ch) {
+        const int cur = ch & 1;
+        const bool more = ch + 1 < chunks;
+        if (more) fetch((ch + 1) * STE_TR);
         // one instruction: lane l supplies A(i = l % 32, k = l / 32) and B(k = l / 32, j = l % 32)
         const int kr = lane >> 5, c = lane & 31;
+        // all operands of the chunk are requested before its first matrix instruction: one LDS latency per chunk
+        float av[STE_TR / 2 / KS][NB], bv[STE_TR / 2 / KS][NB];
 #pragma unroll
-        for (int k = 0; k < STE_TR; k += 2) {
-            const float a0 = As[k + kr][wi + c], a1 = As[k + kr][wi + 32 + c];
-            const float b0 = Bs[k + kr][wj + c], b1 = Bs[k + kr][wj + 32 + c];
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        for (int k2 = 0; k2 < STE_TR / 2 / KS; ++k2)
+#pragma unroll
+            for (int q = 0; q < NB; ++q) {
+                av[k2][q] = As[cur][2 * (KS * k2 + kh) + kr][wi + 32 * q + c];
+                bv[k2][q] = Bs[cur][2 * (KS * k2 + kh) + kr][wj + 32 * q + c];
+            }
+        __builtin_amdgcn_sched_barrier(0);          // (the scheduler would otherwise sink each read to its use)
+#pragma unroll
+        for (int k2 = 0; k2 < STE_TR / 2 / KS; ++k2)
+#pragma unroll
+            for (int bi = 0; bi < NB; ++bi)
+#pragma unroll
+                for (int bj = 0; bj < NB; ++bj)
+                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[k2][bi], bv[k2][bj], acc[bi][bj], 0, 0, 0);
+        if (more) stash(cur ^ 1);           // the other buffer: every wave left it before the previous barrier
+        __syncthreads();
+    }
+
+    if (KS == 2) {          // (the loop ended with a barrier: the staging buffers are free, but this has its own)
+        __shared__ float red[KS == 2 ? 4 * NB * NB * 16 * 64 : 1];
+        if (kh == 1) {
+#pragma unroll
+            for (int bi = 0; bi < NB; ++bi)
+#pragma unroll
+                for (int bj = 0; bj < NB; ++bj)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) red[((wave * NB * NB + bi * NB + bj) * 16 + v) * 64 + lane] = acc[bi][bj][v];
         }
+        __syncthreads();
+        if (kh == 1) return;
+#pragma unroll
+        for (int bi = 0; bi < NB; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < NB; ++bj)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[bi][bj][v] += red[((wave * NB * NB + bi * NB + bj) * 16 + v) * 64 + lane];
     }
 
     // register v of lane l holds row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 of a 32 x 32 block
 #pragma unroll
-    for (int bi = 0; bi < 2; ++bi) {
+    for (int bi = 0; bi < NB; ++bi) {
 #pragma unroll
-        for (int bj = 0; bj < 2; ++bj) {
+        for (int bj = 0; bj < NB; ++bj) {
             const int j = j0 + wj + 32 * bj + (lane & 31);
+            float ov[16];                   // the mask's operand first, all 16 requests together (c and o never overlap)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int i = i0 + wi + 32 * bi + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                if (i < p.I && j < p.J) {
-                    const size_t at = (size_t)i * (size_t)p.J + (size_t)j;
-                    p.c[at] = ste_inside(p.o[at], p.so, p.Q) ? acc[bi][bj][v] : 0.0f;
-                }
+                ov[v] = (FULL || (i < p.I && j < p.J)) ? p.o[(size_t)i * (size_t)p.J + (size_t)j] : 0.0f;
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = i0 + wi + 32 * bi + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                if (FULL || (i < p.I && j < p.J))
+                    p.c[(size_t)i * (size_t)p.J + (size_t)j] = ste_inside(ov[v], p.so, p.Q) ? acc[bi][bj][v] : 0.0f;
             }
         }
     }
 }
 
-// db[n] = sum_m dy[m][n]: 32 columns per workgroup, 8 threads per column take every eighth row, fixed order
-__global__ __launch_bounds__(STE_THREADS) void ste_colsum_kernel(const float *__restrict__ dy, float *__restrict__ db, int M, int N) {
-    __shared__ float part[8][32];
+// db[n] = sum_m dy[m][n]: 32 columns per workgroup, 32 threads per column take every 32nd row with four running sums
+// each; fixed order, so the result does not depend on the launch
+constexpr int STE_COLSUM_THREADS = 1024;
+__global__ __launch_bounds__(STE_COLSUM_THREADS) void ste_colsum_kernel(const float *__restrict__ dy, float *__restrict__ db, int M, int N) {
+    __shared__ float part[32][33];
     const int c = threadIdx.x & 31, ph = threadIdx.x >> 5;
     const int n = blockIdx.x * 32 + c;
-    float s = 0.0f;
-    if (n < N)
-        for (int m = ph; m < M; m += 8) s += dy[(size_t)m * (size_t)N + (size_t)n];
-    part[ph][c] = s;
+    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+    if (n < N) {
+        const float *q = dy + n;
+        int m = ph;
+        for (; m + 96 < M; m += 128) {
+            s0 += q[(size_t)m * (size_t)N];
+            s1 += q[(size_t)(m + 32) * (size_t)N];
+            s2 += q[(size_t)(m + 64) * (size_t)N];
+            s3 += q[(size_t)(m + 96) * (size_t)N];
+        }
+        for (; m < M; m += 32) s0 += q[(size_t)m * (size_t)N];
+    }
+    part[ph][c] = (s0 + s1) + (s2 + s3);
     __syncthreads();
     if (ph == 0 && n < N) {
         float t = part[0][c];
 #pragma unroll
-        for (int q = 1; q < 8; ++q) t += part[q][c];
+        for (int q = 1; q < 32; ++q) t += part[q][c];
         db[n] = t;
     }
 }

@@ -51,7 +51,10 @@ def check(got, want, bound, R):
 
 
 CASES = [(1, 1, 1), (3, 5, 2), (64, 256, 128), (130, 129, 131), (257, 40, 300), (128, 128, 128), (300, 260, 17), (17, 1000, 33),
-         (512, 16, 1), (1, 300, 513)]
+         (512, 16, 1), (1, 300, 513),
+         # launch shapes of the larger products: 64-tiles with four waves (ragged, whole), 128-tiles with four waves (ragged,
+         # whole) and with eight (ragged)
+         (1600, 1300, 24), (1664, 1280, 32), (2100, 4100, 40), (2048, 4096, 64), (2000, 1700, 20)]
 
 
 @pytest.mark.parametrize("bits,clip", [(8, 0.6), (4, 1.0), (12, 0.8)])
