@@ -21,9 +21,9 @@ struct FastDiv {
     __device__ __forceinline__ uint32_t div(uint32_t n) const { return (uint32_t)(((uint64_t)n * M) >> k); }
 };
 
-__global__ void fill_u32_kernel(uint32_t *p, uint32_t v, size_t n) {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = v;
+__global__ void fill_u32_kernel(uint32_t *p, uint32_t v, size_t n) {       // any grid: strides over n
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
 }
 
 // max |x|: the bit pattern of a non-negative float orders like an unsigned integer, so the final

@@ -1739,6 +1739,33 @@ def test_chained_transposed_convolutions(B, case):
         assert bits_equal(host(o2), y2), rep
 
 
+def test_chain_prepare_clears_copies_beyond_4_mib(B):
+    """The consumer's padded input copy (here 4.7 MB) is cleared as a whole when the chain is prepared, whatever the
+    handle's workspace held before: the same handle first runs an unpadded layer whose copy fills those bytes."""
+    bits, N, C0, C1, C2, HW = 6, 64, 8, 64, 16, 32
+    rng = np.random.default_rng(77)
+    lut = wl.make_lut(bits)
+    L = B.Lut(lut, bits)
+    th = orc.host_threads()
+    x = rng.standard_normal((N, C0, HW, HW)).astype(np.float32)
+    w1 = wl.random_i8(rng, (C1, C0, 3, 3), bits, "gauss"); w2 = wl.random_i8(rng, (C2, C1, 3, 3), bits, "gauss")
+    s_x = orc.scale_from_amax(orc.absmax(x), bits)
+    acc1 = orc.approx_conv2d(lut, bits, orc.quantize(x, s_x, bits), w1, (1, 1), (1, 1), threads=th)
+    y1 = orc.relu(orc.dequant(acc1, np.float32(s_x) * np.float32(0.02), N, C1, HW * HW)).reshape(acc1.shape)
+    s_y = orc.scale_from_amax(orc.absmax(y1), bits)
+    acc2 = orc.approx_conv2d(lut, bits, orc.quantize(y1, s_y, bits), w2, (1, 1), (1, 1), threads=th)
+    y2 = orc.dequant(acc2, np.float32(s_y) * np.float32(0.01), N, C2, HW * HW).reshape(acc2.shape)
+    pa = B.adapt_weights_pack_conv2d(L, dev(w1)); pb = B.adapt_weights_pack_conv2d(L, dev(w2))
+    junk = dev((rng.standard_normal((N, C1, HW + 2, HW + 2)) + 3).astype(np.float32))         # no zero codes anywhere
+    B.adapt_conv2d_layer_f32(pb, junk, 0.1, 1.0, (1, 1), (0, 0))
+    B.adapt_conv2d_chain_prepare(pb, N, HW, HW, (1, 1), (1, 1), (1, 1))
+    o1 = torch.empty(acc1.shape, dtype=torch.float32, device="cuda"); o2 = torch.empty(acc2.shape, dtype=torch.float32, device="cuda")
+    B.adapt_conv2d_layer_chain_f32(pa, dev(x), s_x, np.float32(s_x) * np.float32(0.02), o1, (1, 1), (1, 1), act=B.ACT_RELU, next_pw=pb, s_next=s_y)
+    B.adapt_conv2d_layer_chain_f32(pb, None, s_y, np.float32(s_y) * np.float32(0.01), o2, (1, 1), (1, 1), (1, 1), in_shape=(N, HW, HW))
+    assert bits_equal(host(o1), y1)
+    assert bits_equal(host(o2), y2)
+
+
 def test_transposed_chain_refusals(B):
     L = B.Lut(wl.make_lut(8), 8)
     rng = np.random.default_rng(6)
