@@ -74,6 +74,31 @@ inline unsigned ew_grid(size_t work_items) {
     return (unsigned)g;
 }
 
+// Debugging aid: with ADAPT_POISON_ALLOC set in the environment every device allocation of the library is filled with
+// 0xA5 bytes before use, so that code which relies on fresh memory being zero shows up in the tests.
+bool poison_on() {
+    static const bool v = getenv("ADAPT_POISON_ALLOC") != nullptr;
+    return v;
+}
+hipError_t dbg_poison(void *p, size_t bytes, hipStream_t s) {
+    if (!poison_on() || !p || bytes < 4) return hipSuccess;
+    adapt::fill_u32_kernel<<<4096, 256, 0, s>>>(static_cast<uint32_t *>(p), 0xA5A5A5A5u, bytes / 4);
+    return hipGetLastError();
+}
+hipError_t dbg_malloc_async(void **p, size_t bytes, hipStream_t s) {
+    hipError_t e = hipMallocAsync(p, bytes, s);
+    if (e == hipSuccess) e = dbg_poison(*p, bytes, s);
+    return e;
+}
+hipError_t dbg_malloc(void **p, size_t bytes) {
+    hipError_t e = hipMalloc(p, bytes);
+    if (e == hipSuccess && poison_on()) {
+        e = dbg_poison(*p, bytes, nullptr);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+    }
+    return e;
+}
+
 // Scratch memory of one call.  Plain entry points take it from the stream-ordered allocator and give it back in stream
 // order; a packed-weights handle keeps one grow-only buffer, so that its calls allocate nothing once they have run at
 // their largest size (they can then be recorded into a HIP graph).
@@ -84,14 +109,14 @@ struct Workspace {
 
 int ws_get(Workspace *cache, size_t bytes, hipStream_t s, void **out) {
     if (!cache) {
-        HIP_TRY(hipMallocAsync(out, bytes, s));
+        HIP_TRY(dbg_malloc_async(out, bytes, s));
         return ADAPT_OK;
     }
     if (cache->bytes < bytes) {
         if (cache->ptr) HIP_TRY(hipFree(cache->ptr));       // waits for the device: no earlier call still uses it
         cache->ptr = nullptr;
         cache->bytes = 0;
-        HIP_TRY(hipMalloc(&cache->ptr, bytes));
+        HIP_TRY(dbg_malloc(&cache->ptr, bytes));
         cache->bytes = bytes;
     }
     *out = cache->ptr;
@@ -234,7 +259,7 @@ int adapt_lut_create(adapt_lut **out, int bits, const int32_t *table_host) {
                 else e = half == 0 ? (uint16_t)(v & 0xffffu) : (uint16_t)(v >> 16);
                 img[(size_t)w * l->rs + a] = e;
             }
-        hipError_t e = hipMalloc((void **)&l->img_dev[half], (size_t)l->img_bytes);
+        hipError_t e = dbg_malloc((void **)&l->img_dev[half], (size_t)l->img_bytes);
         if (e == hipSuccess) e = hipMemcpy(l->img_dev[half], img.data(), (size_t)l->img_bytes, hipMemcpyHostToDevice);
         // plain copy indexed by the two's-complement wrap of the operands: [a & mask][w & mask]
         std::vector<uint16_t> plain((size_t)n * n);
@@ -242,7 +267,7 @@ int adapt_lut_create(adapt_lut **out, int bits, const int32_t *table_host) {
         for (int a = -hh; a < hh; ++a)
             for (int w = -hh; w < hh; ++w)
                 plain[(size_t)(a & (n - 1)) * n + (w & (n - 1))] = img[(size_t)(w + hh) * l->rs + (a + hh)];
-        if (e == hipSuccess) e = hipMalloc((void **)&l->lut16_dev[half], plain.size() * 2);
+        if (e == hipSuccess) e = dbg_malloc((void **)&l->lut16_dev[half], plain.size() * 2);
         if (e == hipSuccess) e = hipMemcpy(l->lut16_dev[half], plain.data(), plain.size() * 2, hipMemcpyHostToDevice);
         if (e != hipSuccess) {
             for (int j = 0; j < 2; ++j) {
@@ -430,7 +455,7 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     uint32_t *wofs = nullptr;
     int rc = ADAPT_OK;
     if (!prepacked) {
-        HIP_TRY(hipMallocAsync((void **)&wofs, (size_t)Ktot * Npad * ngroups * sizeof(uint32_t), s));
+        HIP_TRY(dbg_malloc_async((void **)&wofs, (size_t)Ktot * Npad * ngroups * sizeof(uint32_t), s));
         const size_t pack_n = (size_t)Ktot * Npad;
         adapt::pack_row_offsets_kernel<<<dim3((unsigned)((pack_n + 255) / 256), (unsigned)ngroups), 256, 0, s>>>(
             w, wofs, (int)Ktot, g.N, Npad, g.Cin, g.taps, g.wt ? (int)adapt::MODE_CONVT : g.mode, 1 << (bits - 1), (1 << bits) - 1,
@@ -901,7 +926,7 @@ const uint4 *ensure_wide(const adapt_weights *h, hipStream_t s) {
     if (h->dtw_dev) return h->dtw_dev;
     if (h->storage != 0 || h->pair_g || !h->w8_dev || !h->lut || h->Cc % 4 != 0 || h->dt_bytes == 0) return nullptr;
     uint4 *d = nullptr;
-    if (hipMalloc((void **)&d, h->dt_bytes) != hipSuccess) {
+    if (dbg_malloc((void **)&d, h->dt_bytes) != hipSuccess) {
         (void)hipGetLastError();
         return nullptr;
     }
@@ -1189,7 +1214,7 @@ int with_temp_tables(const adapt_lut *lut, const int8_t *w, const LinesShape &q,
     uint4 *dt[2] = {nullptr, nullptr};
     int rc = ADAPT_OK;
     for (int half = 0; half <= lut->storage; ++half) {
-        hipError_t e = hipMallocAsync((void **)&dt[half], q.dt_bytes, s);
+        hipError_t e = dbg_malloc_async((void **)&dt[half], q.dt_bytes, s);
         if (e != hipSuccess) {
             rc = fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "hipMallocAsync(tables): %s", hipGetErrorString(e));
             break;
@@ -1253,8 +1278,8 @@ int convt_any(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *a
             uint4 *dt[2] = {nullptr, nullptr};
             int32_t *zsum = nullptr;
             int rc = ADAPT_OK;
-            hipError_t e = hipMallocAsync((void **)&zsum, (size_t)Cout * kh * kw * sizeof(int32_t), s);
-            for (int half = 0; half <= lut->storage && e == hipSuccess; ++half) e = hipMallocAsync((void **)&dt[half], all, s);
+            hipError_t e = dbg_malloc_async((void **)&zsum, (size_t)Cout * kh * kw * sizeof(int32_t), s);
+            for (int half = 0; half <= lut->storage && e == hipSuccess; ++half) e = dbg_malloc_async((void **)&dt[half], all, s);
             if (e != hipSuccess)
                 rc = fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "hipMallocAsync(tables): %s", hipGetErrorString(e));
             if (rc == ADAPT_OK) rc = pack_convt(lut, w, q, kh, kw, stride, dt, zsum, s);
@@ -1375,7 +1400,7 @@ static int weights_pack(adapt_weights **out, const adapt_lut *lut, const int8_t 
     h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0; h->dtw_dev = nullptr; h->dtw_digits = 0; h->dtw_c = 0; h->wofs_cell_dev = nullptr;
     {   // copy of the weights (for table orders made later)
         const size_t wbytes = (size_t)N * Cin * kh * kw;
-        hipError_t e = hipMalloc((void **)&h->w8_dev, wbytes);
+        hipError_t e = dbg_malloc((void **)&h->w8_dev, wbytes);
         if (e == hipSuccess) e = hipMemcpyAsync(h->w8_dev, w_dev, wbytes, hipMemcpyDeviceToDevice, (hipStream_t)stream);
         if (e != hipSuccess) {
             if (h->w8_dev) (void)hipFree(h->w8_dev);
@@ -1386,7 +1411,7 @@ static int weights_pack(adapt_weights **out, const adapt_lut *lut, const int8_t 
     if (kind == 0) {
         h->wofs_npad = ((N + 15) / 16) * 16;
         const size_t pack_n = (size_t)Cin * h->wofs_npad;
-        hipError_t e = hipMalloc((void **)&h->wofs_dev, pack_n * sizeof(uint32_t));
+        hipError_t e = dbg_malloc((void **)&h->wofs_dev, pack_n * sizeof(uint32_t));
         if (e != hipSuccess) {
             delete h;
             return fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "%s: hipMalloc: %s", who, hipGetErrorString(e));
@@ -1395,7 +1420,7 @@ static int weights_pack(adapt_weights **out, const adapt_lut *lut, const int8_t 
             w_dev, h->wofs_dev, Cin, N, h->wofs_npad, Cin, 1, (int)adapt::MODE_GEMM, 1 << (lut->bits - 1), (1 << lut->bits) - 1, lut->rs * 2);
     }
     for (int half = 0; half <= lut->storage; ++half) {
-        hipError_t e = hipMalloc((void **)&h->dt_dev[half], q.dt_bytes);
+        hipError_t e = dbg_malloc((void **)&h->dt_dev[half], q.dt_bytes);
         if (e != hipSuccess) {
             const size_t want = q.dt_bytes;
             adapt_weights_destroy(h);
@@ -1457,15 +1482,15 @@ int adapt_weights_pack_conv_transpose2d(adapt_weights **out, const adapt_lut *lu
     h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0; h->dtw_dev = nullptr; h->dtw_digits = 0; h->dtw_c = 0; h->wofs_cell_dev = nullptr;
     h->phased = kh % stride == 0 && kw % stride == 0 && stride <= 8;
     const size_t wbytes = (size_t)Cout * Cin * kh * kw;
-    hipError_t e = hipMalloc((void **)&h->w8_dev, wbytes);
+    hipError_t e = dbg_malloc((void **)&h->w8_dev, wbytes);
     if (e == hipSuccess) e = hipMemcpyAsync(h->w8_dev, w_dev, wbytes, hipMemcpyDeviceToDevice, (hipStream_t)stream);
     {   // row offsets for the whole-table kernel, both forms
         const int taps = kh * kw, hoff = 1 << (lut->bits - 1), mask = (1 << lut->bits) - 1;
         h->wofs_npad = ((Cout + 15) / 16) * 16;
         h->wofs1_npad = ((Cout * taps + 15) / 16) * 16;
         const size_t n0 = (size_t)taps * Cin * h->wofs_npad, n1 = (size_t)Cin * h->wofs1_npad;
-        if (e == hipSuccess) e = hipMalloc((void **)&h->wofs_dev, n0 * sizeof(uint32_t));
-        if (e == hipSuccess) e = hipMalloc((void **)&h->wofs1_dev, n1 * sizeof(uint32_t));
+        if (e == hipSuccess) e = dbg_malloc((void **)&h->wofs_dev, n0 * sizeof(uint32_t));
+        if (e == hipSuccess) e = dbg_malloc((void **)&h->wofs1_dev, n1 * sizeof(uint32_t));
         if (e == hipSuccess) {
             adapt::pack_row_offsets_kernel<<<(unsigned)((n0 + 255) / 256), 256, 0, (hipStream_t)stream>>>(
                 w_dev, h->wofs_dev, taps * Cin, Cout, h->wofs_npad, Cin, taps, (int)adapt::MODE_CONVT, hoff, mask, lut->rs * 2);
@@ -1480,8 +1505,8 @@ int adapt_weights_pack_conv_transpose2d(adapt_weights **out, const adapt_lut *lu
             h->phased = false;      // too large to hold: this handle keeps to the plain form
         } else {
             h->Cp = q.Cp; h->Cc = q.Cc; h->n_tiles = q.n_tiles; h->dt_bytes = all;
-            e = hipMalloc((void **)&h->zsum_dev, (size_t)Cout * kh * kw * sizeof(int32_t));
-            for (int half = 0; half <= lut->storage && e == hipSuccess; ++half) e = hipMalloc((void **)&h->dt_dev[half], all);
+            e = dbg_malloc((void **)&h->zsum_dev, (size_t)Cout * kh * kw * sizeof(int32_t));
+            for (int half = 0; half <= lut->storage && e == hipSuccess; ++half) e = dbg_malloc((void **)&h->dt_dev[half], all);
             if (e == hipSuccess) {
                 rc = pack_convt(lut, w_dev, q, kh, kw, stride, h->dt_dev, h->zsum_dev, (hipStream_t)stream);
                 if (rc != ADAPT_OK) {
@@ -1635,7 +1660,7 @@ int adapt_mse_from_histogram(const uint32_t *counts_dev, int bins, float amax, i
     if (!counts_dev || !calib_max_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_mse_from_histogram: NULL pointer");
     hipStream_t s = (hipStream_t)stream;
     double *err = nullptr;
-    HIP_TRY(hipMallocAsync((void **)&err, (size_t)bins * sizeof(double), s));
+    HIP_TRY(dbg_malloc_async((void **)&err, (size_t)bins * sizeof(double), s));
     const float width = amax / (float)bins;
     adapt::mse_candidates_kernel<<<(unsigned)((bins + 255) / 256), 256, 0, s>>>(counts_dev, bins, width, (float)((1 << (bits - 1)) - 1), err);
     hipError_t e = hipGetLastError();
@@ -1969,7 +1994,7 @@ static int ensure_cell_offsets(const adapt_weights *h, int Hs, int G, hipStream_
     if (h->wofs_cell_dev) return ADAPT_OK;
     const size_t n = (size_t)Hs * G * Hs;
     uint32_t *d = nullptr;
-    HIP_TRY(hipMalloc((void **)&d, n * sizeof(uint32_t)));
+    HIP_TRY(dbg_malloc((void **)&d, n * sizeof(uint32_t)));
     adapt::pack_row_offsets_cell_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(h->w8_dev, d, Hs, G, 1 << (h->bits - 1),
                                                                                   (1 << h->bits) - 1, h->lut->rs * 2);
     hipError_t e = hipGetLastError();
@@ -2188,8 +2213,8 @@ int adapt_lut16_create(adapt_lut16 **out, int bits, const int32_t *table_host) {
     l->bits = bits; l->t_dev = nullptr; l->device = 0;
     int32_t *tmp = nullptr;
     (void)hipGetDevice(&l->device);
-    hipError_t e = hipMalloc((void **)&l->t_dev, bytes);
-    if (e == hipSuccess) e = hipMalloc((void **)&tmp, bytes);
+    hipError_t e = dbg_malloc((void **)&l->t_dev, bytes);
+    if (e == hipSuccess) e = dbg_malloc((void **)&tmp, bytes);
     if (e == hipSuccess) e = hipMemcpy(tmp, table_host, bytes, hipMemcpyHostToDevice);
     if (e == hipSuccess) {
         adapt::big_transpose_kernel<<<ew_grid(bytes / 4), 256, 0, nullptr>>>(tmp, l->t_dev, bits);
@@ -2224,7 +2249,7 @@ int adapt_lut16_create_from_func(adapt_lut16 **out, int kind, int param, int bit
     if (!l) return fail(ADAPT_ERR_OUT_OF_MEMORY, "adapt_lut16_create_from_func: host allocation failed");
     l->bits = bits; l->t_dev = nullptr; l->device = 0;
     (void)hipGetDevice(&l->device);
-    hipError_t e = hipMalloc((void **)&l->t_dev, entries * sizeof(int32_t));
+    hipError_t e = dbg_malloc((void **)&l->t_dev, entries * sizeof(int32_t));
     if (e == hipSuccess) {
         adapt::big_table_from_func_kernel<<<ew_grid(entries), 256, 0, nullptr>>>(l->t_dev, bits, kind, param);
         e = hipGetLastError();
@@ -2277,7 +2302,7 @@ int run_big(const adapt_lut16 *lut, int kind, int param, const int16_t *x, const
     const long long wgs = (long long)((p.M + threads - 1) / threads) * (p.Npad / NT);
     if (wgs > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "too many workgroups");
     int32_t *words = nullptr;
-    HIP_TRY(hipMallocAsync((void **)&words, (size_t)(K > 0 ? K : 1) * p.Npad * sizeof(int32_t), s));
+    HIP_TRY(dbg_malloc_async((void **)&words, (size_t)(K > 0 ? K : 1) * p.Npad * sizeof(int32_t), s));
     int rc = ADAPT_OK;
     if (K > 0) {
         const size_t n = (size_t)K * p.Npad;
