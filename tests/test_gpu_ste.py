@@ -63,6 +63,10 @@ def test_ste_linear_backward_matches_oracle(B, M, K, N, bits, clip):
     dy, x, w, s_x, s_w = make(M, K, N, bits, M * 7 + K * 3 + N + bits, clip)
     if M * K > 4:
         x.flat[3] = np.nan                      # no gradient there; its fake-quantised value is 0
+    if M * K > 40:                              # exact ties of the rounding and values around the clipping point
+        Q = (1 << (bits - 1)) - 1
+        x.flat[4:20] = (np.arange(16) - 8 + 0.5).astype(np.float32) * s_x
+        x.flat[20:24] = np.array([Q + 0.5, -(Q + 0.5), Q, Q + 0.49], np.float32) * s_x
     dx, dw, db = B.adapt_ste_linear_backward_f32(dev(dy), dev(x), dev(w), s_x, s_w, bits)
     torch.cuda.synchronize()
     ox, ow, ob = ste.ste_linear_backward(dy, x, w, s_x, s_w, bits)
