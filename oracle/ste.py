@@ -74,3 +74,11 @@ def ste_linear_backward_bound(dy, x, w, s_x, s_w, bits):
     xh = np.abs(fake_quant(x, s_x, bits).astype(np.float64))
     wh = np.abs(fake_quant(w, s_w, bits).astype(np.float64))
     return dy64 @ wh, dy64.T @ xh, dy64.sum(axis=0)
+
+
+def sgd_step(w, g, lr) -> np.ndarray:
+    """One plain SGD step in fp32 (Sec. IV-A: the paper retrains with SGD): w - lr * g, the product rounded, then the difference."""
+    w = np.asarray(w, dtype=np.float32)
+    g = np.asarray(g, dtype=np.float32)
+    prod = (np.float32(lr) * g).astype(np.float32)
+    return (w - prod).astype(np.float32)

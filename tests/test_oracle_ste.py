@@ -94,3 +94,11 @@ def test_element_that_sets_a_max_abs_scale_keeps_its_gradient(bits):
 def test_zero_sized_inputs():
     dx, dw, db = ste.ste_linear_backward(np.zeros((0, 3), np.float32), np.zeros((0, 5), np.float32), np.zeros((3, 5), np.float32), 1.0, 1.0, 8)
     assert dx.shape == (0, 5) and dw.shape == (3, 5) and not dw.any() and not db.any()
+
+
+def test_sgd_step_hand_values_and_two_roundings():
+    np.testing.assert_array_equal(ste.sgd_step([1.0, 2.0, -3.0], [0.5, -4.0, 0.25], 0.5), np.array([0.75, 4.0, -3.125], np.float32))
+    # (1 + 2^-12)^2 = 1 + 2^-11 + 2^-24 rounds (tie to even) to 1 + 2^-11: the difference is exactly 0 when the product is
+    # rounded on its own, and -2^-24 if product and difference were fused
+    a = np.float32(1 + 2.0 ** -12)
+    assert ste.sgd_step([np.float32(1 + 2.0 ** -11)], [a], a)[0] == 0.0
