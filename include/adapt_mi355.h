@@ -395,6 +395,12 @@ int adapt_approx_conv2d_func_i16(int kind, int param, int bits, const int16_t *x
 int adapt_ste_linear_backward_f32(const float *dy_dev, const float *x_dev, const float *w_dev, int M, int K, int N, float s_x,
                                   float s_w, int bits, float *dx_dev, float *dw_dev, float *db_dev, void *stream);
 
+/* One plain stochastic-gradient step, the optimiser the paper retrains with (Sec. IV-A, "Quantization and retraining":
+ * SGD, learning rate 1e-4): w[i] <- w[i] - lr * g[i] in fp32, the product and the difference rounded separately.
+ * w_dev, g_dev: n floats each on the device, distinct; in place on w_dev.  Asynchronous on `stream`.
+ * Errors: ADAPT_ERR_INVALID_ARGUMENT (NULL pointer, w_dev == g_dev), ADAPT_ERR_HIP. */
+int adapt_sgd_step_f32(float *w_dev, const float *g_dev, size_t n, float lr, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

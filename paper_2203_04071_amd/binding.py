@@ -36,7 +36,7 @@ EXPORTS = [
     "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32", "adapt_lstm_cell_q_f32", "adapt_lstm_step_f32", "adapt_gru_step_f32", "adapt_rnn_step_f32", "adapt_gru_cell_f32", "adapt_rnn_cell_f32",
     "adapt_lut16_create", "adapt_lut16_create_from_func", "adapt_lut16_destroy", "adapt_lut16_bits", "adapt_quantize_i16_f32",
     "adapt_approx_linear_i16", "adapt_approx_conv2d_i16", "adapt_approx_linear_func_i16", "adapt_approx_conv2d_func_i16",
-    "adapt_ste_linear_backward_f32",
+    "adapt_ste_linear_backward_f32", "adapt_sgd_step_f32",
 ]
 
 
@@ -115,6 +115,7 @@ def load() -> ctypes.CDLL:
     L.adapt_lstm_cell_q_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, vp, f32, i32, i32, i32, vp]
     L.adapt_gru_cell_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, vp, vp, f32, i32, i32, i32, vp]
     L.adapt_rnn_cell_f32.argtypes = [vp, vp, f32, f32, vp, i32, vp, vp, f32, i32, i32, i32, vp]
+    L.adapt_sgd_step_f32.argtypes = [vp, vp, sz, f32, vp]
     L.adapt_ste_linear_backward_f32.argtypes = [vp, vp, vp, i32, i32, i32, f32, f32, i32, vp, vp, vp, vp]
     for name in EXPORTS:
         if name != "adapt_last_error":
@@ -723,3 +724,10 @@ def adapt_ste_linear_backward_f32(dy, x, w, s_x, s_w, bits, want=("dx", "dw", "d
                                               float(s_x), float(s_w), int(bits), _ptr(dx, torch.float32), _ptr(dw, torch.float32),
                                               _ptr(db, torch.float32), _stream(stream)))
     return dx, dw, db
+
+
+def adapt_sgd_step_f32(w, g, lr, stream=None):
+    """w <- w - lr * g in place."""
+    assert w.shape == g.shape
+    _chk(load().adapt_sgd_step_f32(_ptr(w, torch.float32), _ptr(g, torch.float32), w.numel(), float(lr), _stream(stream)))
+    return w

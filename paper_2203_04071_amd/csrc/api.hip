@@ -2100,6 +2100,15 @@ int adapt_add_f32(const float *a_dev, const float *b_dev, float *y_dev, size_t n
     return ADAPT_OK;
 }
 
+int adapt_sgd_step_f32(float *w_dev, const float *g_dev, size_t n, float lr, void *stream) {
+    if ((!w_dev || !g_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_sgd_step_f32: NULL pointer");
+    if (w_dev == g_dev && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_sgd_step_f32: w_dev and g_dev must differ");
+    if (!n) return ADAPT_OK;
+    adapt::sgd_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(w_dev, g_dev, n, lr);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
 int adapt_avgpool_hw_f32(const float *x_dev, float *y_dev, size_t NC, size_t HW, void *stream) {
     if ((!x_dev || !y_dev) && NC) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_avgpool_hw_f32: NULL pointer");
     if (HW == 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_avgpool_hw_f32: HW is 0");

@@ -255,6 +255,12 @@ __global__ __launch_bounds__(EW_THREADS) void add_kernel(const float *a, const f
     }
 }
 
+// plain stochastic-gradient step of the retraining loop: w <- w - lr * g, the product and the difference rounded separately
+__global__ __launch_bounds__(EW_THREADS) void sgd_kernel(float *__restrict__ w, const float *__restrict__ g, size_t n, float lr) {
+    const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) w[i] = w[i] - lr * g[i];
+}
+
 // one thread per (n, c) plane: the sum order (row-major, sequential) is part of the definition
 __global__ __launch_bounds__(EW_THREADS) void avgpool_kernel(const float *__restrict__ x, float *__restrict__ y,
                                                              size_t NC, size_t HW) {

@@ -137,3 +137,47 @@ def test_ste_refusals(B):
     rc = L.adapt_ste_linear_backward_f32(None, d[1].data_ptr(), d[2].data_ptr(), 4, 8, 4, ctypes.c_float(s_x), ctypes.c_float(s_w), 8,
                                          None, d[0].data_ptr(), None, None)           # dy missing
     assert rc == -1
+
+
+@pytest.mark.parametrize("n", [0, 1, 255, 4099, 1 << 21])
+def test_sgd_step_bit_exact(B, n):
+    rng = np.random.default_rng(n)
+    w = rng.standard_normal(n).astype(np.float32); g = rng.standard_normal(n).astype(np.float32)
+    if n:
+        a = np.float32(1 + 2.0 ** -12)
+        w[0], g[0] = np.float32(1 + 2.0 ** -11), a          # exactly 0 with separate roundings at lr = a
+    for lr in (np.float32(1 + 2.0 ** -12), np.float32(1e-4)):
+        wd = dev(w)
+        B.adapt_sgd_step_f32(wd, dev(g), lr)
+        got = wd.cpu().numpy(); want = ste.sgd_step(w, g, lr)
+        assert (got.view(np.uint32) == want.view(np.uint32)).all()
+
+
+def test_retraining_loop_recovers_error_of_an_approximate_layer(B):
+    """Forward through the multiplier table, straight-through backward, SGD: the loop of Sec. III-A on a synthetic
+    regression task.  The student starts from perturbed weights; its loss through the approximate layer must fall
+    well below the start and end near the floor set by 8-bit quantisation and the table's error."""
+    from paper_2203_04071_amd import workloads as wl
+    import oracle as orc
+    rng = np.random.default_rng(11)
+    M, K, N, bits = 256, 64, 32, 8
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    w_true = (rng.standard_normal((N, K)) * 0.2).astype(np.float32)
+    target = dev((x.astype(np.float64) @ w_true.astype(np.float64).T).astype(np.float32))
+    w = dev((w_true + 0.1 * rng.standard_normal((N, K))).astype(np.float32))
+    xd = dev(x)
+    L = B.Lut(wl.make_lut(bits), bits)
+    s_x = orc.scale_from_amax(orc.absmax(x), bits)
+    losses = []
+    for it in range(40):
+        s_w = orc.scale_from_amax(float(B.adapt_absmax_f32(w).item()), bits)
+        pw = B.adapt_weights_pack_linear(L, B.adapt_quantize_f32(w, s_w, bits))
+        y = B.adapt_linear_layer_f32(pw, xd, s_x, np.float32(s_x) * np.float32(s_w))
+        diff = y - target
+        losses.append(float((diff * diff).mean().item()))
+        dy = (diff * (2.0 / diff.numel())).contiguous()
+        _, dw, _ = B.adapt_ste_linear_backward_f32(dy, xd, w, s_x, s_w, bits, want=("dw",))
+        B.adapt_sgd_step_f32(w, dw, 4.0)
+        B.adapt_weights_destroy(pw)
+    assert losses[-1] < 0.05 * losses[0], losses[::8]
+    assert all(b < a * 1.05 for a, b in zip(losses, losses[1:])), losses       # no blow-up on the way
