@@ -82,3 +82,47 @@ def sgd_step(w, g, lr) -> np.ndarray:
     g = np.asarray(g, dtype=np.float32)
     prod = (np.float32(lr) * g).astype(np.float32)
     return (w - prod).astype(np.float32)
+
+
+def _conv_out(H, k, s, p, d):
+    return (H + 2 * p - d * (k - 1) - 1) // s + 1
+
+
+def ste_conv2d_backward(dy, x, w, stride, pad, dil, s_x, s_w, bits, absolute=False):
+    """Straight-through backward pass of an approximate 2-D convolution (groups = 1), tap by tap from the definition
+    y[n][o][oy][ox] = sum_{c,ky,kx} x^[n][c][oy s - p + ky d][ox s - p + kx d] * w^[o][c][ky][kx] (zero outside the image):
+
+        dw[o][c][ky][kx] = inside(w) * sum_{n,oy,ox} dy[n][o][oy][ox] * x^[n][c][oy s - p + ky d][ox s - p + kx d]
+        dx[n][c][iy][ix] = inside(x) * sum over the (o, ky, kx, oy, ox) whose tap lands on (iy, ix) of dy * w^
+        db[o]            = sum_{n,oy,ox} dy[n][o][oy][ox]
+
+    dy [N][O][Ho][Wo], x [N][C][H][W], w [O][C][kh][kw] fp32 -> fp64 results.  absolute=True: the same sums over
+    absolute values without the masks (what an fp32 accumulation error is measured against)."""
+    dy = np.asarray(dy, dtype=np.float32).astype(np.float64)
+    x32 = np.asarray(x, dtype=np.float32)
+    w32 = np.asarray(w, dtype=np.float32)
+    N, C, H, W = x32.shape
+    O, C2, kh, kw = w32.shape
+    (sh, sw), (ph, pw), (dh, dw_) = stride, pad, dil
+    Ho, Wo = _conv_out(H, kh, sh, ph, dh), _conv_out(W, kw, sw, pw, dw_)
+    assert C2 == C and dy.shape == (N, O, Ho, Wo)
+    xh = fake_quant(x32, s_x, bits).astype(np.float64)
+    wh = fake_quant(w32, s_w, bits).astype(np.float64)
+    if absolute:
+        dy, xh, wh = np.abs(dy), np.abs(xh), np.abs(wh)
+    xp = np.zeros((N, C, H + 2 * ph, W + 2 * pw))
+    xp[:, :, ph:ph + H, pw:pw + W] = xh
+    dxp = np.zeros_like(xp)
+    dwt = np.zeros((O, C, kh, kw))
+    for ky in range(kh):
+        for kx in range(kw):
+            ys = slice(ky * dh, ky * dh + (Ho - 1) * sh + 1, sh)
+            xs = slice(kx * dw_, kx * dw_ + (Wo - 1) * sw + 1, sw)
+            dwt[:, :, ky, kx] = np.einsum("nohw,nchw->oc", dy, xp[:, :, ys, xs])
+            dxp[:, :, ys, xs] += np.einsum("nohw,oc->nchw", dy, wh[:, :, ky, kx])
+    dx = dxp[:, :, ph:ph + H, pw:pw + W]
+    db = dy.sum(axis=(0, 2, 3))
+    if not absolute:
+        dx = dx * clip_inside(x32, s_x, bits)
+        dwt = dwt * clip_inside(w32, s_w, bits)
+    return dx, dwt, db

@@ -102,3 +102,50 @@ def test_sgd_step_hand_values_and_two_roundings():
     # rounded on its own, and -2^-24 if product and difference were fused
     a = np.float32(1 + 2.0 ** -12)
     assert ste.sgd_step([np.float32(1 + 2.0 ** -11)], [a], a)[0] == 0.0
+
+
+@pytest.mark.parametrize("geo", [
+    # N, C, H, W, O, kh, kw, stride, pad, dil
+    (2, 3, 7, 6, 4, 3, 3, (1, 1), (1, 1), (1, 1)),
+    (1, 2, 9, 8, 3, 3, 2, (2, 1), (0, 1), (1, 2)),
+    (3, 4, 6, 6, 2, 1, 1, (1, 1), (0, 0), (1, 1)),
+    (2, 2, 10, 11, 3, 5, 3, (2, 3), (2, 1), (2, 1)),
+])
+def test_conv_backward_equals_autograd_of_fake_quantised_convolution(geo):
+    import torch.nn.functional as F
+    N, C, H, W, O, kh, kw, stride, pad, dil = geo
+    bits, s_x, s_w = 6, 2.0 ** -3, 2.0 ** -5
+    Q = (1 << (bits - 1)) - 1
+    rng = np.random.default_rng(sum(geo[:7]))
+    x = (rng.integers(-4 * Q - 12, 4 * Q + 13, size=(N, C, H, W)) * 0.25 * s_x).astype(np.float32)
+    w = (rng.integers(-4 * Q - 12, 4 * Q + 13, size=(O, C, kh, kw)) * 0.25 * s_w).astype(np.float32)
+    xt = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    wt = torch.tensor(w, dtype=torch.float64, requires_grad=True)
+    bt = torch.zeros(O, dtype=torch.float64, requires_grad=True)
+
+    def fq(t, s):
+        r = t / s
+        r = r + (torch.round(r) - r).detach()
+        return torch.clamp(r, -Q, Q) * s
+
+    y = F.conv2d(fq(xt, s_x), fq(wt, s_w), bt, stride, pad, dil)
+    dy = rng.standard_normal(tuple(y.shape)).astype(np.float32)
+    (y * torch.tensor(dy, dtype=torch.float64)).sum().backward()
+    dx, dw, db = ste.ste_conv2d_backward(dy, x, w, stride, pad, dil, s_x, s_w, bits)
+    assert (np.abs(x) > Q * s_x).any()
+    np.testing.assert_allclose(dx, xt.grad.numpy(), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(dw, wt.grad.numpy(), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(db, bt.grad.numpy(), rtol=1e-12, atol=1e-13)
+
+
+def test_conv_backward_of_a_1x1_convolution_is_the_linear_backward():
+    rng = np.random.default_rng(3)
+    N, C, H, W, O, bits = 2, 5, 3, 4, 6, 8
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32); w = rng.standard_normal((O, C, 1, 1)).astype(np.float32) * 0.3
+    dy = rng.standard_normal((N, O, H, W)).astype(np.float32)
+    dx, dw, db = ste.ste_conv2d_backward(dy, x, w, (1, 1), (0, 0), (1, 1), 0.011, 0.004, bits)
+    rows = lambda t: np.ascontiguousarray(np.transpose(t, (0, 2, 3, 1)).reshape(-1, t.shape[1]))
+    lx, lw, lb = ste.ste_linear_backward(rows(dy), rows(x), w.reshape(O, C), 0.011, 0.004, bits)
+    np.testing.assert_allclose(rows(dx), lx, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(dw.reshape(O, C), lw, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(db, lb, rtol=1e-13)
