@@ -395,6 +395,26 @@ int adapt_approx_conv2d_func_i16(int kind, int param, int bits, const int16_t *x
 int adapt_ste_linear_backward_f32(const float *dy_dev, const float *x_dev, const float *w_dev, int M, int K, int N, float s_x,
                                   float s_w, int bits, float *dx_dev, float *dw_dev, float *db_dev, void *stream);
 
+/* The same backward pass for an approximate 2-D convolution with groups = 1 (Sec. III-A "Retraining"; Sec. III-B: the
+ * convolution as a matrix product over the unfolded input).  With x^ = s_x q(x), w^ = s_w q(w) and zero outside the image:
+ *     dw[o][c][ky][kx] = inside(w) * sum_{n,oy,ox} dy[n][o][oy][ox] * x^[n][c][oy s - p + ky d][ox s - p + kx d]
+ *     dx[n][c][iy][ix] = inside(x) * sum over the (o, ky, kx, oy, ox) whose tap lands on (iy, ix) of dy * w^
+ *     db[o]            = sum_{n,oy,ox} dy[n][o][oy][ox]
+ * dy_dev [N][Cout][Ho][Wo], x_dev [N][Cin][H][W], w_dev [Cout][Cin][kh][kw]: fp32 device pointers, dense; geometry as in
+ * adapt_approx_conv2d.  dx_dev, dw_dev, db_dev: shapes of x, w and [Cout]; fully overwritten; NULL = not computed; none
+ * may alias an input.  workspace_dev: device memory of at least the number of bytes that
+ * adapt_ste_conv2d_backward_workspace reports for the same arguments (want_dx / want_dw: whether dx_dev / dw_dev are
+ * given), aligned to 256 bytes, owned by the caller, contents undefined afterwards; it holds dy as rows and the unfolded
+ * matrices.  fp32 sums (matrix instructions for the products, a fixed tap order for dx).  Asynchronous on `stream`, no
+ * allocation.  Errors: ADAPT_ERR_INVALID_ARGUMENT (pointers, geometry, bits, scales, workspace too small or misaligned),
+ * ADAPT_ERR_UNSUPPORTED (N Ho Wo above 65535 * 64), ADAPT_ERR_HIP. */
+int adapt_ste_conv2d_backward_workspace(int N, int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w, int pad_h,
+                                        int pad_w, int dil_h, int dil_w, int want_dx, int want_dw, size_t *bytes);
+int adapt_ste_conv2d_backward_f32(const float *dy_dev, const float *x_dev, const float *w_dev, int N, int Cin, int H, int W, int Cout,
+                                  int kh, int kw, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, float s_x,
+                                  float s_w, int bits, float *dx_dev, float *dw_dev, float *db_dev, void *workspace_dev,
+                                  size_t workspace_bytes, void *stream);
+
 /* One plain stochastic-gradient step, the optimiser the paper retrains with (Sec. IV-A, "Quantization and retraining":
  * SGD, learning rate 1e-4): w[i] <- w[i] - lr * g[i] in fp32, the product and the difference rounded separately.
  * w_dev, g_dev: n floats each on the device, distinct; in place on w_dev.  Asynchronous on `stream`.

@@ -36,7 +36,7 @@ EXPORTS = [
     "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32", "adapt_lstm_cell_q_f32", "adapt_lstm_step_f32", "adapt_gru_step_f32", "adapt_rnn_step_f32", "adapt_gru_cell_f32", "adapt_rnn_cell_f32",
     "adapt_lut16_create", "adapt_lut16_create_from_func", "adapt_lut16_destroy", "adapt_lut16_bits", "adapt_quantize_i16_f32",
     "adapt_approx_linear_i16", "adapt_approx_conv2d_i16", "adapt_approx_linear_func_i16", "adapt_approx_conv2d_func_i16",
-    "adapt_ste_linear_backward_f32", "adapt_sgd_step_f32",
+    "adapt_ste_linear_backward_f32", "adapt_sgd_step_f32", "adapt_ste_conv2d_backward_workspace", "adapt_ste_conv2d_backward_f32",
 ]
 
 
@@ -116,6 +116,8 @@ def load() -> ctypes.CDLL:
     L.adapt_gru_cell_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, vp, vp, f32, i32, i32, i32, vp]
     L.adapt_rnn_cell_f32.argtypes = [vp, vp, f32, f32, vp, i32, vp, vp, f32, i32, i32, i32, vp]
     L.adapt_sgd_step_f32.argtypes = [vp, vp, sz, f32, vp]
+    L.adapt_ste_conv2d_backward_workspace.argtypes = [i32] * 15 + [ctypes.POINTER(sz)]
+    L.adapt_ste_conv2d_backward_f32.argtypes = [vp, vp, vp] + [i32] * 13 + [f32, f32, i32, vp, vp, vp, vp, sz, vp]
     L.adapt_ste_linear_backward_f32.argtypes = [vp, vp, vp, i32, i32, i32, f32, f32, i32, vp, vp, vp, vp]
     for name in EXPORTS:
         if name != "adapt_last_error":
@@ -731,3 +733,24 @@ def adapt_sgd_step_f32(w, g, lr, stream=None):
     assert w.shape == g.shape
     _chk(load().adapt_sgd_step_f32(_ptr(w, torch.float32), _ptr(g, torch.float32), w.numel(), float(lr), _stream(stream)))
     return w
+
+
+def adapt_ste_conv2d_backward_f32(dy, x, w, stride, pad, dil, s_x, s_w, bits, want=("dx", "dw", "db"), workspace=None, stream=None):
+    """dy [N][Cout][Ho][Wo], x [N][Cin][H][W], w [Cout][Cin][kh][kw] fp32 -> (dx, dw, db); entries not in `want` are None.
+    workspace: a uint8 device tensor to reuse (allocated here when None or too small)."""
+    N, Cin, H, W = x.shape
+    Cout, Cin2, kh, kw = w.shape
+    assert Cin == Cin2 and dy.shape[:2] == (N, Cout)
+    geo = (N, Cin, H, W, Cout, kh, kw, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1])
+    need = ctypes.c_size_t(0)
+    _chk(load().adapt_ste_conv2d_backward_workspace(*geo, 1 if "dx" in want else 0, 1 if "dw" in want else 0, ctypes.byref(need)))
+    if workspace is None or workspace.numel() < need.value:
+        workspace = torch.empty(max(need.value, 256), dtype=torch.uint8, device=x.device)
+    dx = torch.empty_like(x) if "dx" in want else None
+    dw = torch.empty_like(w) if "dw" in want else None
+    db = torch.empty((Cout,), dtype=torch.float32, device=x.device) if "db" in want else None
+    _chk(load().adapt_ste_conv2d_backward_f32(_ptr(dy, torch.float32), _ptr(x, torch.float32), _ptr(w, torch.float32), *geo, float(s_x),
+                                              float(s_w), int(bits), _ptr(dx, torch.float32), _ptr(dw, torch.float32),
+                                              _ptr(db, torch.float32), ctypes.c_void_p(workspace.data_ptr()), workspace.numel(),
+                                              _stream(stream)))
+    return dx, dw, db

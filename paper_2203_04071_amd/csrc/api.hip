@@ -380,6 +380,116 @@ int adapt_ste_linear_backward_f32(const float *dy_dev, const float *x_dev, const
     return ADAPT_OK;
 }
 
+namespace {
+struct SteConvPlan {
+    adapt::SteConvGeo g;
+    long long M, K;
+    size_t rows_bytes, col_bytes, total;
+};
+int ste_conv_plan(SteConvPlan *pl, int N, int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w, int pad_h, int pad_w,
+                  int dil_h, int dil_w, bool want_dx, bool want_dw, const char *who) {
+    if (N < 0 || Cin < 1 || H < 1 || W < 1 || Cout < 1 || kh < 1 || kw < 1 || stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0 ||
+        dil_h < 1 || dil_w < 1)
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
+    const long long Ho = ((long long)H + 2LL * pad_h - (long long)dil_h * (kh - 1) - 1) / stride_h + 1;
+    const long long Wo = ((long long)W + 2LL * pad_w - (long long)dil_w * (kw - 1) - 1) / stride_w + 1;
+    if ((long long)H + 2LL * pad_h < (long long)dil_h * (kh - 1) + 1 || (long long)W + 2LL * pad_w < (long long)dil_w * (kw - 1) + 1)
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: the filter does not fit the padded image", who);
+    pl->M = (long long)N * Ho * Wo;
+    pl->K = (long long)Cin * kh * kw;
+    if (pl->M > 65535LL * 64 || pl->K > 0x7fffffffLL || Ho > 0x7fffffffLL || Wo > 0x7fffffffLL || (long long)N * Cin * H * W > (1LL << 40))
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor too large (N Ho Wo is limited to %d)", who, 65535 * 64);
+    pl->g = adapt::SteConvGeo{N, Cin, H, W, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, (int)Ho, (int)Wo};
+    auto up = [](size_t b) { return (b + 255) / 256 * 256; };
+    pl->rows_bytes = up((size_t)pl->M * Cout * sizeof(float));
+    pl->col_bytes = up((size_t)pl->M * (size_t)pl->K * sizeof(float));
+    pl->total = pl->rows_bytes + (want_dw ? pl->col_bytes : 0) + (want_dx ? pl->col_bytes : 0);
+    return ADAPT_OK;
+}
+}  // namespace
+
+int adapt_ste_conv2d_backward_workspace(int N, int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w, int pad_h,
+                                        int pad_w, int dil_h, int dil_w, int want_dx, int want_dw, size_t *bytes) {
+    const char *who = "adapt_ste_conv2d_backward_workspace";
+    if (!bytes) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
+    SteConvPlan pl;
+    int rc = ste_conv_plan(&pl, N, Cin, H, W, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, want_dx != 0, want_dw != 0, who);
+    if (rc) return rc;
+    *bytes = pl.total;
+    return ADAPT_OK;
+}
+
+int adapt_ste_conv2d_backward_f32(const float *dy_dev, const float *x_dev, const float *w_dev, int N, int Cin, int H, int W, int Cout,
+                                  int kh, int kw, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, float s_x,
+                                  float s_w, int bits, float *dx_dev, float *dw_dev, float *db_dev, void *workspace_dev,
+                                  size_t workspace_bytes, void *stream) {
+    const char *who = "adapt_ste_conv2d_backward_f32";
+    if (bits < 2 || bits > 16) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bits=%d not in [2,16]", who, bits);
+    if (!(s_x > 0.0f) || !(s_w > 0.0f) || s_x > 3.0e38f || s_w > 3.0e38f)
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: scales must be finite and > 0", who);
+    SteConvPlan pl;
+    int rc = ste_conv_plan(&pl, N, Cin, H, W, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, dx_dev != nullptr,
+                           dw_dev != nullptr, who);
+    if (rc) return rc;
+    if (pl.M > 0 && (!dy_dev || !x_dev || !w_dev)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
+    for (const void *q : {(const void *)dy_dev, (const void *)x_dev, (const void *)w_dev, (const void *)dx_dev, (const void *)dw_dev,
+                          (const void *)db_dev})
+        if (reinterpret_cast<uintptr_t>(q) & 3u) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: pointer not aligned to 4 bytes", who);
+    if ((dx_dev && (dx_dev == x_dev || dx_dev == dy_dev || dx_dev == w_dev)) || (dw_dev && (dw_dev == w_dev || dw_dev == dy_dev || dw_dev == x_dev)))
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: a gradient must not alias an input", who);
+    if (!dx_dev && !dw_dev && !db_dev) return ADAPT_OK;
+    hipStream_t s = (hipStream_t)stream;
+    const adapt::SteConvGeo &g = pl.g;
+    const float Q = (float)((1 << (bits - 1)) - 1);
+    const size_t w_elems = (size_t)Cout * (size_t)pl.K, x_elems = (size_t)N * Cin * H * W;
+    if (pl.M == 0) {        // no samples: the weight and bias gradients are zero, there is no input gradient
+        if (dw_dev) adapt::fill_u32_kernel<<<ew_grid(w_elems), 256, 0, s>>>(reinterpret_cast<uint32_t *>(dw_dev), 0u, w_elems);
+        if (db_dev) adapt::fill_u32_kernel<<<ew_grid((size_t)Cout), 256, 0, s>>>(reinterpret_cast<uint32_t *>(db_dev), 0u, (size_t)Cout);
+        HIP_TRY(hipGetLastError());
+        return ADAPT_OK;
+    }
+    if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 255u) || workspace_bytes < pl.total)
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: workspace of %zu bytes, aligned to 256, needed (adapt_ste_conv2d_backward_workspace)", who,
+                    pl.total);
+    char *ws = static_cast<char *>(workspace_dev);
+    float *rows = reinterpret_cast<float *>(ws);
+    float *col = dw_dev ? reinterpret_cast<float *>(ws + pl.rows_bytes) : nullptr;
+    float *dcol = dx_dev ? reinterpret_cast<float *>(ws + pl.rows_bytes + (dw_dev ? pl.col_bytes : 0)) : nullptr;
+    const int M = (int)pl.M, K = (int)pl.K, P = g.Ho * g.Wo;
+    const size_t rows_n = (size_t)M * Cout, col_n = (size_t)M * K;
+    if (rows_n < 0x7fffffffull) adapt::ste_rows_from_nchw_kernel<uint32_t><<<ew_grid(rows_n), 256, 0, s>>>(dy_dev, rows, Cout, P, rows_n);
+    else adapt::ste_rows_from_nchw_kernel<size_t><<<ew_grid(rows_n), 256, 0, s>>>(dy_dev, rows, Cout, P, rows_n);
+    HIP_TRY(hipGetLastError());
+    if (dw_dev) {           // dw [Cout][K] = inside(w) * rows^T [Cout][M] . fq(col(x)) [M][K]
+        if (col_n < 0x7fffffffull) adapt::ste_im2col_kernel<uint32_t><<<ew_grid(col_n), 256, 0, s>>>(x_dev, col, g, col_n);
+        else adapt::ste_im2col_kernel<size_t><<<ew_grid(col_n), 256, 0, s>>>(x_dev, col, g, col_n);
+        HIP_TRY(hipGetLastError());
+        adapt::SteParams p{};
+        p.a = rows; p.b = col; p.o = w_dev; p.c = dw_dev;
+        p.I = Cout; p.J = K; p.R = M; p.lda = Cout;
+        p.sb = s_x; p.so = s_w; p.Q = Q;
+        launch_ste_gemm(p, true, true, s);          // (both operands lie in the workspace)
+        HIP_TRY(hipGetLastError());
+    }
+    if (dx_dev) {           // dcol [M][K] = rows [M][Cout] . fq(w) [Cout][K]; dx = inside(x) * the taps of dcol gathered onto the image
+        adapt::SteParams p{};
+        p.a = rows; p.b = w_dev; p.o = nullptr; p.c = dcol;
+        p.I = M; p.J = K; p.R = Cout; p.lda = Cout;
+        p.sb = s_w; p.so = 1.0f; p.Q = Q;
+        launch_ste_gemm(p, false, aligned16(w_dev), s);
+        HIP_TRY(hipGetLastError());
+        if (x_elems < 0x7fffffffull && col_n < 0x7fffffffull)
+            adapt::ste_col2im_kernel<uint32_t><<<ew_grid(x_elems), 256, 0, s>>>(dcol, x_dev, dx_dev, g, s_x, Q, x_elems);
+        else adapt::ste_col2im_kernel<size_t><<<ew_grid(x_elems), 256, 0, s>>>(dcol, x_dev, dx_dev, g, s_x, Q, x_elems);
+        HIP_TRY(hipGetLastError());
+    }
+    if (db_dev) {
+        adapt::ste_colsum_kernel<<<(unsigned)((Cout + 31) / 32), adapt::STE_COLSUM_THREADS, 0, s>>>(rows, db_dev, M, Cout);
+        HIP_TRY(hipGetLastError());
+    }
+    return ADAPT_OK;
+}
+
 }  // extern "C"
 
 /* ------------------------------------------------------------------ table-lookup matrix products */

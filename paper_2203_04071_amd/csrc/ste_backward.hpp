@@ -24,7 +24,7 @@ constexpr int STE_THREADS = 256;    // four waves, 2 x 2 over the workgroup's ou
 struct SteParams {
     const float *a;     // A_T: element (i, r) at a[r * lda + i]; else at a[i * lda + r]
     const float *b;     // [R][J], fake-quantised with scale sb while it is staged
-    const float *o;     // [I][J], decides the clip mask with scale so
+    const float *o;     // [I][J], decides the clip mask with scale so; nullptr: no mask
     float *c;           // [I][J]
     int I, J, R, lda;
     float sb, so, Q;
@@ -186,13 +186,13 @@ __global__ __launch_bounds__(STE_THREADS * KS) void ste_gemm_kernel(SteParams p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int i = i0 + wi + 32 * bi + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                ov[v] = (FULL || (i < p.I && j < p.J)) ? p.o[(size_t)i * (size_t)p.J + (size_t)j] : 0.0f;
+                ov[v] = (p.o && (FULL || (i < p.I && j < p.J))) ? p.o[(size_t)i * (size_t)p.J + (size_t)j] : 0.0f;
             }
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int i = i0 + wi + 32 * bi + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                 if (FULL || (i < p.I && j < p.J))
-                    p.c[(size_t)i * (size_t)p.J + (size_t)j] = ste_inside(ov[v], p.so, p.Q) ? acc[bi][bj][v] : 0.0f;
+                    p.c[(size_t)i * (size_t)p.J + (size_t)j] = (!p.o || ste_inside(ov[v], p.so, p.Q)) ? acc[bi][bj][v] : 0.0f;
             }
         }
     }
@@ -224,6 +224,70 @@ __global__ __launch_bounds__(STE_COLSUM_THREADS) void ste_colsum_kernel(const fl
 #pragma unroll
         for (int q = 1; q < 32; ++q) t += part[q][c];
         db[n] = t;
+    }
+}
+
+// ---- convolution (groups = 1): the same two products over the unfolded input --------------------------------------
+// y[m][o] = sum_k col(x^)[m][k] * w^[o][k] with m = (n, oy, ox), k = (c, ky, kx) (Sec. III-B: the convolution as a matrix
+// product over the unfolded input), so dw = mask(w) . dy_rows^T . fq(col(x)) and dcol = dy_rows . fq(w), and dx gathers
+// dcol back onto the image (a fixed order) under mask(x).  The unfolded matrices live in a workspace of the caller.
+struct SteConvGeo {
+    int N, C, H, W, O, kh, kw, sh, sw, ph, pw, dh, dw, Ho, Wo;
+};
+
+// dy [N][O][P] -> rows [N * P][O]
+template <typename Idx>
+__global__ __launch_bounds__(256) void ste_rows_from_nchw_kernel(const float *__restrict__ dy, float *__restrict__ rows, int O, int P, size_t total) {
+    const Idx stride = (Idx)gridDim.x * 256;
+    for (Idx i = (Idx)blockIdx.x * 256 + threadIdx.x; i < (Idx)total; i += stride) {
+        const Idx o = i % (Idx)O, m = i / (Idx)O, n = m / (Idx)P, pix = m % (Idx)P;
+        rows[i] = dy[((size_t)n * O + o) * P + pix];
+    }
+}
+
+// x [N][C][H][W] -> col [N * Ho * Wo][C * kh * kw], zero where a tap lies outside the image
+template <typename Idx>
+__global__ __launch_bounds__(256) void ste_im2col_kernel(const float *__restrict__ x, float *__restrict__ col, SteConvGeo g, size_t total) {
+    const Idx stride = (Idx)gridDim.x * 256;
+    const Idx K = (Idx)g.C * g.kh * g.kw;
+    for (Idx i = (Idx)blockIdx.x * 256 + threadIdx.x; i < (Idx)total; i += stride) {
+        const Idx k = i % K, m = i / K;
+        const int kx = (int)(k % (Idx)g.kw), ky = (int)((k / (Idx)g.kw) % (Idx)g.kh), c = (int)(k / (Idx)(g.kw * g.kh));
+        const int ox = (int)(m % (Idx)g.Wo), oy = (int)((m / (Idx)g.Wo) % (Idx)g.Ho);
+        const Idx n = m / (Idx)(g.Wo * g.Ho);
+        const int iy = oy * g.sh - g.ph + ky * g.dh, ix = ox * g.sw - g.pw + kx * g.dw;
+        float v = 0.0f;
+        if (iy >= 0 && iy < g.H && ix >= 0 && ix < g.W) v = x[(((size_t)n * g.C + c) * g.H + iy) * g.W + ix];
+        col[i] = v;
+    }
+}
+
+// dx[n][c][iy][ix] = inside(x) * sum over the taps (ky, kx ascending) that land on (iy, ix) of dcol[(n, oy, ox)][(c, ky, kx)]
+template <typename Idx>
+__global__ __launch_bounds__(256) void ste_col2im_kernel(const float *__restrict__ dcol, const float *__restrict__ x, float *__restrict__ dx,
+                                                         SteConvGeo g, float s_x, float Q, size_t total) {
+    const Idx stride = (Idx)gridDim.x * 256;
+    const size_t K = (size_t)g.C * g.kh * g.kw;
+    for (Idx i = (Idx)blockIdx.x * 256 + threadIdx.x; i < (Idx)total; i += stride) {
+        const int ix = (int)(i % (Idx)g.W), iy = (int)((i / (Idx)g.W) % (Idx)g.H);
+        const Idx nc = i / (Idx)(g.W * g.H);
+        const int c = (int)(nc % (Idx)g.C);
+        const Idx n = nc / (Idx)g.C;
+        float s = 0.0f;
+        for (int ky = 0; ky < g.kh; ++ky) {
+            const int ty = iy + g.ph - ky * g.dh;
+            if (ty < 0 || ty % g.sh) continue;
+            const int oy = ty / g.sh;
+            if (oy >= g.Ho) continue;
+            for (int kx = 0; kx < g.kw; ++kx) {
+                const int tx = ix + g.pw - kx * g.dw;
+                if (tx < 0 || tx % g.sw) continue;
+                const int ox = tx / g.sw;
+                if (ox >= g.Wo) continue;
+                s += dcol[(((size_t)n * g.Ho + oy) * g.Wo + ox) * K + ((size_t)c * g.kh + ky) * g.kw + kx];
+            }
+        }
+        dx[i] = ste_inside(x[i], s_x, Q) ? s : 0.0f;
     }
 }
 

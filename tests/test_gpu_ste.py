@@ -181,3 +181,65 @@ def test_retraining_loop_recovers_error_of_an_approximate_layer(B):
         B.adapt_weights_destroy(pw)
     assert losses[-1] < 0.05 * losses[0], losses[::8]
     assert all(b < a * 1.05 for a, b in zip(losses, losses[1:])), losses       # no blow-up on the way
+
+
+CONV_CASES = [
+    # N, C, H, W, O, kh, kw, stride, pad, dil, bits
+    (2, 3, 7, 6, 4, 3, 3, (1, 1), (1, 1), (1, 1), 8),
+    (1, 2, 9, 8, 3, 3, 2, (2, 1), (0, 1), (1, 2), 6),
+    (3, 4, 6, 6, 2, 1, 1, (1, 1), (0, 0), (1, 1), 8),
+    (2, 2, 10, 11, 3, 5, 3, (2, 3), (2, 1), (2, 1), 4),
+    (8, 16, 16, 16, 32, 3, 3, (1, 1), (1, 1), (1, 1), 8),          # whole tiles: 2048 rows, 144 columns
+    (4, 64, 32, 32, 64, 3, 3, (1, 1), (1, 1), (1, 1), 8),          # an eighth of the benchmark layer's batch
+    (5, 13, 17, 19, 21, 3, 3, (2, 2), (1, 1), (1, 1), 7),          # nothing divides anything
+    (16, 16, 32, 32, 16, 3, 3, (2, 2), (1, 1), (1, 1), 8),         # a stride-2 layer of the CNN configuration
+    (0, 3, 5, 5, 2, 3, 3, (1, 1), (1, 1), (1, 1), 8),              # empty batch
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_ste_conv2d_backward_matches_oracle(B, case):
+    N, C, H, W, O, kh, kw, stride, pad, dil, bits = case
+    rng = np.random.default_rng(sum(case[:7]) + bits)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    w = (rng.standard_normal((O, C, kh, kw)) * 0.1).astype(np.float32)
+    Ho = (H + 2 * pad[0] - dil[0] * (kh - 1) - 1) // stride[0] + 1
+    Wo = (W + 2 * pad[1] - dil[1] * (kw - 1) - 1) // stride[1] + 1
+    dy = rng.standard_normal((N, O, Ho, Wo)).astype(np.float32)
+    Q = (1 << (bits - 1)) - 1
+    s_x = np.float32(0.7 * (np.abs(x).max() if x.size else 1.0) / Q)
+    s_w = np.float32(0.8 * np.abs(w).max() / Q)
+    dx, dw, db = B.adapt_ste_conv2d_backward_f32(dev(dy), dev(x), dev(w), stride, pad, dil, s_x, s_w, bits)
+    torch.cuda.synchronize()
+    ox, ow, ob = ste.ste_conv2d_backward(dy, x, w, stride, pad, dil, s_x, s_w, bits)
+    bx, bw, bb = ste.ste_conv2d_backward(dy, x, w, stride, pad, dil, s_x, s_w, bits, absolute=True)
+    M = N * Ho * Wo
+    if x.size > 100:
+        assert (ox == 0).any() and (ow == 0).any()
+    check(dx, ox, bx, O + kh * kw)
+    check(dw, ow, bw, M)
+    check(db, ob, bb, M)
+    # only one of the gradients, with a workspace that is reused
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    dx2, dw2, db2 = B.adapt_ste_conv2d_backward_f32(dev(dy), dev(x), dev(w), stride, pad, dil, s_x, s_w, bits, want=("dx",), workspace=ws)
+    assert dw2 is None and db2 is None and torch.equal(dx2, dx)
+
+
+def test_ste_conv2d_refusals(B):
+    import ctypes
+    L = B.load()
+    x = torch.zeros((2, 3, 8, 8), device="cuda"); w = torch.zeros((4, 3, 3, 3), device="cuda"); dy = torch.zeros((2, 4, 8, 8), device="cuda")
+    dx = torch.empty_like(x)
+    geo = (2, 3, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, 1)
+    need = ctypes.c_size_t(0)
+    assert L.adapt_ste_conv2d_backward_workspace(*geo, 1, 1, ctypes.byref(need)) == 0 and need.value > 0
+    ws = torch.empty(need.value, dtype=torch.uint8, device="cuda")
+    f = lambda wsp, nbytes, g=geo, bits=8: L.adapt_ste_conv2d_backward_f32(dy.data_ptr(), x.data_ptr(), w.data_ptr(), *g, ctypes.c_float(1.0),
+                                                                          ctypes.c_float(1.0), bits, dx.data_ptr(), None, None, wsp, nbytes, None)
+    assert f(ws.data_ptr(), need.value) == 0
+    assert f(ws.data_ptr(), 16) == -1                      # too small
+    assert f(None, need.value) == -1
+    assert f(ws.data_ptr() + 4, need.value) == -1          # misaligned
+    assert f(ws.data_ptr(), need.value, bits=1) == -1
+    assert f(ws.data_ptr(), need.value, g=(2, 3, 2, 2, 4, 5, 5, 1, 1, 0, 0, 1, 1)) == -1       # filter larger than the image
+    torch.cuda.synchronize()
