@@ -191,6 +191,18 @@ def build_step(cfg_id, bits, torch, B, gnet, wl, eager=False):
             B.adapt_ste_linear_backward_f32(dy, x, w, s_x, s_w, 7, out=outs)
         name = "extra: straight-through backward pass of a linear layer, 6400 x 512 -> 2048, 7-bit operands (dx, dw, db)"
         return core, core, 2 * M * K * N, name, outs
+    if cfg_id == 11:    # retraining: straight-through backward pass of the headline convolution layer (configuration 2's shape)
+        c = wl.config2()
+        x = dev(c["x"]); w = dev(c["w"])
+        dy = dev(np.random.default_rng(1234 + 11).standard_normal((32, 64, 32, 32)).astype(np.float32))
+        s_x = gnet.calibrated_scale(x, 8)
+        s_w = gnet.calibrated_scale(w, 8)
+        ws = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+
+        def core():
+            B.adapt_ste_conv2d_backward_f32(dy, x, w, (1, 1), (1, 1), (1, 1), s_x, s_w, 8, workspace=ws)
+        name = "extra: straight-through backward pass of the 3x3 convolution layer, batch 32, 64->64 ch, 32x32, 8-bit operands (dx, dw, db)"
+        return core, core, 2 * 32768 * 576 * 64, name, ws
     raise SystemExit(f"unknown config {cfg_id}")
 
 
@@ -263,6 +275,18 @@ def cpu_baseline(cfg_id, bits, wl):
         dt = time.perf_counter() - t0
         return dict(value=wl.lut_macs_conv2d(8, 64, 32, 32, 64, 3, 3, 1, 1, 1, 1) / dt, unit="LUT-MAC/s", cores=th, kind="oracle",
                     sample="8 of 32 images, one pass")
+    if cfg_id == 11:
+        from oracle import ste
+        c = wl.config2()
+        x = c["x"][:8]
+        dy = np.random.default_rng(1234 + 11).standard_normal((8, 64, 32, 32)).astype(np.float32)
+        s_x = orc.scale_from_amax(orc.absmax(c["x"]), 8)
+        s_w = orc.scale_from_amax(orc.absmax(c["w"]), 8)
+        t0 = time.perf_counter()
+        ste.ste_conv2d_backward(dy, x, c["w"], (1, 1), (1, 1), (1, 1), s_x, s_w, 8)
+        dt = time.perf_counter() - t0
+        return dict(value=4.0 * 8 * 1024 * 576 * 64 / dt, unit="FLOP/s", cores=th, kind="oracle",
+                    sample="8 of 32 images, one pass (fp64; tap by tap with numpy's einsum)")
     if cfg_id == 10:
         from oracle import ste
         M, K, N = 1600, 512, 2048
@@ -291,7 +315,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, help="1-5: the baseline configurations (default 2, the one the metric is quoted on); "
                     "6: separable convolution block, 7: GRU layer, 8 / 9: the layer of 2 with 12-bit operands, table / function form, "
-                    "10: straight-through backward pass of a linear layer "
+                    "10 / 11: straight-through backward pass of a linear / convolution layer "
                     "(rows beyond the baseline, not bench lines of record)")
     ap.add_argument("--bits", type=int, default=8, help="table bits for config 5 (6 or 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -395,10 +419,10 @@ def main():
             roof.update(bound="l1-gather", peak=gpeak / 1e12, frac=achieved / gpeak,
                         peak_model=f"{cus} CUs x {GATHER_LANES_PER_CLK_PER_CU} gathered lanes/clk x {MODEL_CLOCK_GHZ} GHz; "
                                    "1 lookup (4 B from device memory) per LUT-MAC")
-        if args.config == 10:
+        if args.config in (10, 11):
             # two dense fp32 contractions (macs counts the multiply-adds of both): the matrix pipe's fp32 rate
             roof = dict(bound="mfma", achieved=2 * achieved / 1e12, peak=157.3, unit="TFLOP/s", frac=2 * achieved / 157.3e12, traffic=None,
-                        kernel_ms_avg=k_avg, kernel_ms_min=float(kms.min()), covers="both product kernels and the bias-gradient kernel of the call",
+                        kernel_ms_avg=k_avg, kernel_ms_min=float(kms.min()), covers="every kernel of the call (products, bias gradient; convolution: also the unfolding and gathering kernels)",
                         peak_model="published dense fp32 matrix rate of MI355X")
         if args.config == 9:
             # the multiplier as a function: vector integer operations, 64 lanes per clock per compute unit
@@ -412,17 +436,17 @@ def main():
                     traffic=traffic, note="whole network step (all kernels) against the LDS lookup peak")
 
     out = {
-        "metric": ("approximate MACs/sec (LUT-MAC/s), whole step: quantise + table-lookup layer(s) + dequantise" if args.config != 10 else
+        "metric": ("approximate MACs/sec (LUT-MAC/s), whole step: quantise + table-lookup layer(s) + dequantise" if args.config not in (10, 11) else
                    "fp32 FLOP/s of the two gradient contractions (fake quantisation and clip masks included in the time)"),
-        "value": macs / (ms_per_step * 1e-3) * (2 if args.config == 10 else 1),
-        "unit": "LUT-MAC/s" if args.config != 10 else "FLOP/s",
+        "value": macs / (ms_per_step * 1e-3) * (2 if args.config in (10, 11) else 1),
+        "unit": "LUT-MAC/s" if args.config not in (10, 11) else "FLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": ("int8 operands, int16 table, int32 accumulate, fp32 scale" if args.config < 8 else
-                  "f32" if args.config == 10 else
+                  "f32" if args.config in (10, 11) else
                   "int16 operands (12-bit), int32 table or function, int32 accumulate, fp32 scale"),
         "data": "synthetic (seeded)", "prewarm_ms": args.prewarm_ms,
-        "config": {"workload": name, ("lut_macs_per_step" if args.config != 10 else "multiply_adds_per_step"): macs},
+        "config": {"workload": name, ("lut_macs_per_step" if args.config not in (10, 11) else "multiply_adds_per_step"): macs},
         "roofline": roof,
     }
     if not args.no_cpu_baseline:

@@ -47,14 +47,34 @@ int ste_env(const char *name) {
     const char *e = getenv(name);
     return e ? atoi(e) : 0;
 }
-void launch_ste_gemm(const adapt::SteParams &p, bool a_t, bool aligned, hipStream_t s) {
+// Floats of partial sums a split product may need: it is split only below 256 tiles of 64 x 64, into at most
+// 512 / tiles + 1 parts.
+constexpr size_t STE_PARTIAL_FLOATS = (size_t)(512 + 256) * 64 * 64;
+
+// partials != nullptr (STE_PARTIAL_FLOATS floats): a product with few output tiles and a long contraction is split
+// over grid z into partial sums, which ste_reduce_masked_kernel adds in a fixed order.
+void launch_ste_gemm(const adapt::SteParams &p_in, bool a_t, bool aligned, hipStream_t s, float *partials = nullptr) {
     static const int env_tile = ste_env("ADAPT_STE_TILE"), env_ks = ste_env("ADAPT_STE_KS");
+    adapt::SteParams p = p_in;
     const int cus = 256;
     const long long t128 = (((long long)p.I + 127) / 128) * (((long long)p.J + 127) / 128);
     int tile = 4 * t128 >= 3 * cus ? 128 : 64;
     if (env_tile == 64 || env_tile == 128) tile = env_tile;
-    const dim3 grid((unsigned)((p.J + tile - 1) / tile), (unsigned)((p.I + tile - 1) / tile));
-    int ks = (long long)grid.x * grid.y < 2 * cus ? 2 : 1;
+    dim3 grid((unsigned)((p.J + tile - 1) / tile), (unsigned)((p.I + tile - 1) / tile), 1);
+    const int chunks = (p.R + adapt::STE_TR - 1) / adapt::STE_TR;
+    const long long tiles = (long long)grid.x * grid.y;
+    p.cps = chunks > 0 ? chunks : 1;
+    int parts = 1;
+    if (partials && tile == 64 && tiles < cus && chunks >= 8) {
+        int want = (int)((2 * cus + tiles - 1) / tiles);
+        if (want > chunks / 4) want = chunks / 4;                   // at least four chunks per part
+        if (want >= 2) {
+            p.cps = (chunks + want - 1) / want;
+            parts = (chunks + p.cps - 1) / p.cps;
+        }
+    }
+    if (parts > 1) { grid.z = (unsigned)parts; p.c = partials; p.o = nullptr; }
+    int ks = tiles * parts < 2 * cus ? 2 : 1;
     if (env_ks == 1 || env_ks == 2) ks = env_ks;
     const bool full = aligned && p.I % tile == 0 && p.J % tile == 0 && p.R % adapt::STE_TR == 0 && p.lda % 4 == 0 && p.R > 0;
 #define STE_LAUNCH4(AT, T, F) \
@@ -65,6 +85,12 @@ void launch_ste_gemm(const adapt::SteParams &p, bool a_t, bool aligned, hipStrea
     else { if (tile == 128) STE_LAUNCH2(false, 128); else STE_LAUNCH2(false, 64); }
 #undef STE_LAUNCH2
 #undef STE_LAUNCH4
+    if (parts > 1) {
+        const size_t n = (size_t)p.I * (size_t)p.J;
+        const size_t blocks = (n + 255) / 256;
+        adapt::ste_reduce_masked_kernel<<<(unsigned)(blocks < 4096 ? blocks : 4096), 256, 0, s>>>(partials, parts, n, p_in.o, p_in.so, p_in.Q,
+                                                                                                  p_in.c);
+    }
 }
 
 inline unsigned ew_grid(size_t work_items) {
@@ -351,7 +377,7 @@ int adapt_ste_linear_backward_f32(const float *dy_dev, const float *x_dev, const
     if ((want_dx || want_dw) && ((M > 0 && !x_dev) || (N > 0 && !w_dev))) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL x_dev / w_dev", who);
     for (const void *q : {(const void *)dy_dev, (const void *)x_dev, (const void *)w_dev, (const void *)dx_dev, (const void *)dw_dev, (const void *)db_dev})
         if (reinterpret_cast<uintptr_t>(q) & 3u) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: pointer not aligned to 4 bytes", who);
-    if (dx_dev && (dx_dev == x_dev || dx_dev == dy_dev || dx_dev == w_dev) || dw_dev && (dw_dev == w_dev || dw_dev == dy_dev || dw_dev == x_dev))
+    if ((dx_dev && (dx_dev == x_dev || dx_dev == dy_dev || dx_dev == w_dev)) || (dw_dev && (dw_dev == w_dev || dw_dev == dy_dev || dw_dev == x_dev)))
         return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: a gradient must not alias an input", who);
     if (((long long)M + 63) / 64 > 65535 || ((long long)N + 63) / 64 > 65535)
         return fail(ADAPT_ERR_UNSUPPORTED, "%s: M and N are limited to %d", who, 65535 * 64);
@@ -384,7 +410,7 @@ namespace {
 struct SteConvPlan {
     adapt::SteConvGeo g;
     long long M, K;
-    size_t rows_bytes, col_bytes, total;
+    size_t rows_bytes, col_bytes, part_bytes, total;
 };
 int ste_conv_plan(SteConvPlan *pl, int N, int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w, int pad_h, int pad_w,
                   int dil_h, int dil_w, bool want_dx, bool want_dw, const char *who) {
@@ -403,7 +429,8 @@ int ste_conv_plan(SteConvPlan *pl, int N, int Cin, int H, int W, int Cout, int k
     auto up = [](size_t b) { return (b + 255) / 256 * 256; };
     pl->rows_bytes = up((size_t)pl->M * Cout * sizeof(float));
     pl->col_bytes = up((size_t)pl->M * (size_t)pl->K * sizeof(float));
-    pl->total = pl->rows_bytes + (want_dw ? pl->col_bytes : 0) + (want_dx ? pl->col_bytes : 0);
+    pl->part_bytes = up(STE_PARTIAL_FLOATS * sizeof(float));
+    pl->total = pl->rows_bytes + (want_dw ? pl->col_bytes : 0) + (want_dx ? pl->col_bytes : 0) + pl->part_bytes;
     return ADAPT_OK;
 }
 }  // namespace
@@ -455,6 +482,7 @@ int adapt_ste_conv2d_backward_f32(const float *dy_dev, const float *x_dev, const
     float *rows = reinterpret_cast<float *>(ws);
     float *col = dw_dev ? reinterpret_cast<float *>(ws + pl.rows_bytes) : nullptr;
     float *dcol = dx_dev ? reinterpret_cast<float *>(ws + pl.rows_bytes + (dw_dev ? pl.col_bytes : 0)) : nullptr;
+    float *partials = reinterpret_cast<float *>(ws + pl.total - pl.part_bytes);      // used by one kernel pair at a time (stream order)
     const int M = (int)pl.M, K = (int)pl.K, P = g.Ho * g.Wo;
     const size_t rows_n = (size_t)M * Cout, col_n = (size_t)M * K;
     if (rows_n < 0x7fffffffull) adapt::ste_rows_from_nchw_kernel<uint32_t><<<ew_grid(rows_n), 256, 0, s>>>(dy_dev, rows, Cout, P, rows_n);
@@ -468,7 +496,7 @@ int adapt_ste_conv2d_backward_f32(const float *dy_dev, const float *x_dev, const
         p.a = rows; p.b = col; p.o = w_dev; p.c = dw_dev;
         p.I = Cout; p.J = K; p.R = M; p.lda = Cout;
         p.sb = s_x; p.so = s_w; p.Q = Q;
-        launch_ste_gemm(p, true, true, s);          // (both operands lie in the workspace)
+        launch_ste_gemm(p, true, true, s, partials);        // (both operands lie in the workspace)
         HIP_TRY(hipGetLastError());
     }
     if (dx_dev) {           // dcol [M][K] = rows [M][Cout] . fq(w) [Cout][K]; dx = inside(x) * the taps of dcol gathered onto the image
@@ -484,7 +512,13 @@ int adapt_ste_conv2d_backward_f32(const float *dy_dev, const float *x_dev, const
         HIP_TRY(hipGetLastError());
     }
     if (db_dev) {
-        adapt::ste_colsum_kernel<<<(unsigned)((Cout + 31) / 32), adapt::STE_COLSUM_THREADS, 0, s>>>(rows, db_dev, M, Cout);
+        const int Z = N < 16 ? N : 16;
+        if ((size_t)Z * Cout <= STE_PARTIAL_FLOATS && Z > 1) {
+            adapt::ste_bias_grad_nchw_kernel<<<dim3((unsigned)Cout, (unsigned)Z), 256, 0, s>>>(dy_dev, partials, N, Cout, P);
+            adapt::ste_reduce_masked_kernel<<<(unsigned)((Cout + 255) / 256), 256, 0, s>>>(partials, Z, (size_t)Cout, nullptr, 1.0f, Q, db_dev);
+        } else {
+            adapt::ste_bias_grad_nchw_kernel<<<dim3((unsigned)Cout, 1), 256, 0, s>>>(dy_dev, db_dev, N, Cout, P);
+        }
         HIP_TRY(hipGetLastError());
     }
     return ADAPT_OK;

@@ -28,6 +28,7 @@ struct SteParams {
     float *c;           // [I][J]
     int I, J, R, lda;
     float sb, so, Q;
+    int cps;            // chunks of STE_TR contraction indices per grid z: z > 0 writes its partial sums to c + z * I * J
 };
 
 __device__ __forceinline__ float ste_fake_quant(float x, float s, float Q) {
@@ -126,13 +127,15 @@ __global__ __launch_bounds__(STE_THREADS * KS) void ste_gemm_kernel(SteParams p)
         }
     };
 
-    const int chunks = (p.R + STE_TR - 1) / STE_TR;
-    if (chunks > 0) { fetch(0); stash(0); }
+    const int ch0 = blockIdx.z * p.cps;             // this workgroup's share of the contraction
+    const int chunks = max(0, min((p.R + STE_TR - 1) / STE_TR, ch0 + p.cps) - ch0);
+    float *const cout = p.c + (size_t)blockIdx.z * (size_t)p.I * (size_t)p.J;
+    if (chunks > 0) { fetch(ch0 * STE_TR); stash(0); }
     __syncthreads();
     for (int ch = 0; ch < chunks; ++ch) {
         const int cur = ch & 1;
         const bool more = ch + 1 < chunks;
-        if (more) fetch((ch + 1) * STE_TR);
+        if (more) fetch((ch0 + ch + 1) * STE_TR);
         // one instruction: lane l supplies A(i = l % 32, k = l / 32) and B(k = l / 32, j = l % 32)
         const int kr = lane >> 5, c = lane & 31;
         // all operands of the chunk are requested before its first matrix instruction: one LDS latency per chunk
@@ -192,10 +195,41 @@ __global__ __launch_bounds__(STE_THREADS * KS) void ste_gemm_kernel(SteParams p)
             for (int v = 0; v < 16; ++v) {
                 const int i = i0 + wi + 32 * bi + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                 if (FULL || (i < p.I && j < p.J))
-                    p.c[(size_t)i * (size_t)p.J + (size_t)j] = (!p.o || ste_inside(ov[v], p.so, p.Q)) ? acc[bi][bj][v] : 0.0f;
+                    cout[(size_t)i * (size_t)p.J + (size_t)j] = (!p.o || ste_inside(ov[v], p.so, p.Q)) ? acc[bi][bj][v] : 0.0f;
             }
         }
     }
+}
+
+// c[i] = inside(o[i]) * (part[0][i] + part[1][i] + ... + part[S-1][i]), in that order: the partial sums of a product whose
+// contraction was split over grid z
+__global__ __launch_bounds__(256) void ste_reduce_masked_kernel(const float *__restrict__ part, int S, size_t n, const float *__restrict__ o,
+                                                                float so, float Q, float *__restrict__ c) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+        float s = part[i];
+        for (int z = 1; z < S; ++z) s += part[(size_t)z * n + i];
+        c[i] = (!o || ste_inside(o[i], so, Q)) ? s : 0.0f;
+    }
+}
+
+// part[z][o] = sum over the images n = z, z + Z, ... and all pixels of dy[n][o][pix] from the NCHW tensor (grid: O x Z
+// workgroups; every thread a strided share in ascending order, then a fixed tree); ste_reduce_masked_kernel adds the Z parts
+__global__ __launch_bounds__(256) void ste_bias_grad_nchw_kernel(const float *__restrict__ dy, float *__restrict__ db, int N, int O, int P) {
+    __shared__ float part[256];
+    const int o = blockIdx.x;
+    float s = 0.0f;
+    for (int n = blockIdx.y; n < N; n += gridDim.y) {
+        const float *q = dy + ((size_t)n * O + o) * (size_t)P;
+        for (int e = threadIdx.x; e < P; e += 256) s += q[e];
+    }
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) db[(size_t)blockIdx.y * O + o] = part[0];
 }
 
 // db[n] = sum_m dy[m][n]: 32 columns per workgroup, 32 threads per column take every 32nd row with four running sums
@@ -269,10 +303,14 @@ __global__ __launch_bounds__(256) void ste_col2im_kernel(const float *__restrict
     const Idx stride = (Idx)gridDim.x * 256;
     const size_t K = (size_t)g.C * g.kh * g.kw;
     for (Idx i = (Idx)blockIdx.x * 256 + threadIdx.x; i < (Idx)total; i += stride) {
-        const int ix = (int)(i % (Idx)g.W), iy = (int)((i / (Idx)g.W) % (Idx)g.H);
-        const Idx nc = i / (Idx)(g.W * g.H);
-        const int c = (int)(nc % (Idx)g.C);
-        const Idx n = nc / (Idx)g.C;
+        // neighbouring lanes take neighbouring channels of one pixel: their reads of dcol are 4 kh kw bytes apart (one row
+        // of dcol serves them all) instead of a whole row apart; the one store and the one read of x per lane are the
+        // strided side
+        const int c = (int)(i % (Idx)g.C);
+        const Idx pixel = i / (Idx)g.C;
+        const int ix = (int)(pixel % (Idx)g.W), iy = (int)((pixel / (Idx)g.W) % (Idx)g.H);
+        const Idx n = pixel / (Idx)(g.W * g.H);
+        const size_t at = (((size_t)n * g.C + c) * g.H + iy) * g.W + ix;
         float s = 0.0f;
         for (int ky = 0; ky < g.kh; ++ky) {
             const int ty = iy + g.ph - ky * g.dh;
@@ -287,7 +325,7 @@ __global__ __launch_bounds__(256) void ste_col2im_kernel(const float *__restrict
                 s += dcol[(((size_t)n * g.Ho + oy) * g.Wo + ox) * K + ((size_t)c * g.kh + ky) * g.kw + kx];
             }
         }
-        dx[i] = ste_inside(x[i], s_x, Q) ? s : 0.0f;
+        dx[at] = ste_inside(x[at], s_x, Q) ? s : 0.0f;
     }
 }
 
