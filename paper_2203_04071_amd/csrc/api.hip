@@ -407,6 +407,7 @@ int adapt_ste_linear_backward_f32(const float *dy_dev, const float *x_dev, const
 }
 
 namespace {
+adapt::FastDiv fast_div(uint32_t d);
 struct SteConvPlan {
     adapt::SteConvGeo g;
     long long M, K;
@@ -425,7 +426,15 @@ int ste_conv_plan(SteConvPlan *pl, int N, int Cin, int H, int W, int Cout, int k
     pl->K = (long long)Cin * kh * kw;
     if (pl->M > 65535LL * 64 || pl->K > 0x7fffffffLL || Ho > 0x7fffffffLL || Wo > 0x7fffffffLL || (long long)N * Cin * H * W > (1LL << 40))
         return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor too large (N Ho Wo is limited to %d)", who, 65535 * 64);
-    pl->g = adapt::SteConvGeo{N, Cin, H, W, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, (int)Ho, (int)Wo};
+    if ((long long)H * W > 0x7fffffffLL || Ho * Wo > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: an image plane is limited to 2^31 - 1 pixels", who);
+    adapt::SteConvGeo &g = pl->g;
+    g = adapt::SteConvGeo{};
+    g.N = N; g.C = Cin; g.H = H; g.W = W; g.O = Cout; g.kh = kh; g.kw = kw; g.sh = stride_h; g.sw = stride_w; g.ph = pad_h; g.pw = pad_w;
+    g.dh = dil_h; g.dw = dil_w; g.Ho = (int)Ho; g.Wo = (int)Wo;
+    g.dK = fast_div((uint32_t)pl->K); g.dkw = fast_div((uint32_t)kw); g.dkhkw = fast_div((uint32_t)(kh * kw)); g.dWo = fast_div((uint32_t)Wo);
+    g.dHoWo = fast_div((uint32_t)(Ho * Wo)); g.dC = fast_div((uint32_t)Cin); g.dW = fast_div((uint32_t)W); g.dHW = fast_div((uint32_t)(H * W));
+    g.dO = fast_div((uint32_t)Cout); g.dP = fast_div((uint32_t)(Ho * Wo)); g.dsh = fast_div((uint32_t)stride_h); g.dsw = fast_div((uint32_t)stride_w);
     auto up = [](size_t b) { return (b + 255) / 256 * 256; };
     pl->rows_bytes = up((size_t)pl->M * Cout * sizeof(float));
     pl->col_bytes = up((size_t)pl->M * (size_t)pl->K * sizeof(float));
@@ -485,8 +494,8 @@ int adapt_ste_conv2d_backward_f32(const float *dy_dev, const float *x_dev, const
     float *partials = reinterpret_cast<float *>(ws + pl.total - pl.part_bytes);      // used by one kernel pair at a time (stream order)
     const int M = (int)pl.M, K = (int)pl.K, P = g.Ho * g.Wo;
     const size_t rows_n = (size_t)M * Cout, col_n = (size_t)M * K;
-    if (rows_n < 0x7fffffffull) adapt::ste_rows_from_nchw_kernel<uint32_t><<<ew_grid(rows_n), 256, 0, s>>>(dy_dev, rows, Cout, P, rows_n);
-    else adapt::ste_rows_from_nchw_kernel<size_t><<<ew_grid(rows_n), 256, 0, s>>>(dy_dev, rows, Cout, P, rows_n);
+    if (rows_n < 0x7fffffffull) adapt::ste_rows_from_nchw_kernel<uint32_t><<<ew_grid(rows_n), 256, 0, s>>>(dy_dev, rows, g, rows_n);
+    else adapt::ste_rows_from_nchw_kernel<size_t><<<ew_grid(rows_n), 256, 0, s>>>(dy_dev, rows, g, rows_n);
     HIP_TRY(hipGetLastError());
     if (dw_dev) {           // dw [Cout][K] = inside(w) * rows^T [Cout][M] . fq(col(x)) [M][K]
         if (col_n < 0x7fffffffull) adapt::ste_im2col_kernel<uint32_t><<<ew_grid(col_n), 256, 0, s>>>(x_dev, col, g, col_n);

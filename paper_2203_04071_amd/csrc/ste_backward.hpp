@@ -13,6 +13,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "elementwise.hpp"
+
 namespace adapt {
 
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
@@ -267,14 +269,23 @@ __global__ __launch_bounds__(STE_COLSUM_THREADS) void ste_colsum_kernel(const fl
 // dcol back onto the image (a fixed order) under mask(x).  The unfolded matrices live in a workspace of the caller.
 struct SteConvGeo {
     int N, C, H, W, O, kh, kw, sh, sw, ph, pw, dh, dw, Ho, Wo;
+    FastDiv dK, dkw, dkhkw, dWo, dHoWo, dC, dW, dHW, dO, dP, dsh, dsw;      // the divisors of the index decodes below
 };
+
+// n / f.d: multiply-and-shift for 32-bit indices (exact below 2^31), a plain division otherwise
+template <typename Idx>
+__device__ __forceinline__ Idx ste_div(Idx n, const FastDiv &f) {
+    if constexpr (sizeof(Idx) == 4) return (Idx)f.div((uint32_t)n);
+    else return n / (Idx)f.d;
+}
 
 // dy [N][O][P] -> rows [N * P][O]
 template <typename Idx>
-__global__ __launch_bounds__(256) void ste_rows_from_nchw_kernel(const float *__restrict__ dy, float *__restrict__ rows, int O, int P, size_t total) {
+__global__ __launch_bounds__(256) void ste_rows_from_nchw_kernel(const float *__restrict__ dy, float *__restrict__ rows, SteConvGeo g, size_t total) {
     const Idx stride = (Idx)gridDim.x * 256;
+    const int O = g.O, P = g.Ho * g.Wo;
     for (Idx i = (Idx)blockIdx.x * 256 + threadIdx.x; i < (Idx)total; i += stride) {
-        const Idx o = i % (Idx)O, m = i / (Idx)O, n = m / (Idx)P, pix = m % (Idx)P;
+        const Idx m = ste_div<Idx>(i, g.dO), o = i - m * (Idx)O, n = ste_div<Idx>(m, g.dP), pix = m - n * (Idx)P;
         rows[i] = dy[((size_t)n * O + o) * P + pix];
     }
 }
@@ -285,10 +296,11 @@ __global__ __launch_bounds__(256) void ste_im2col_kernel(const float *__restrict
     const Idx stride = (Idx)gridDim.x * 256;
     const Idx K = (Idx)g.C * g.kh * g.kw;
     for (Idx i = (Idx)blockIdx.x * 256 + threadIdx.x; i < (Idx)total; i += stride) {
-        const Idx k = i % K, m = i / K;
-        const int kx = (int)(k % (Idx)g.kw), ky = (int)((k / (Idx)g.kw) % (Idx)g.kh), c = (int)(k / (Idx)(g.kw * g.kh));
-        const int ox = (int)(m % (Idx)g.Wo), oy = (int)((m / (Idx)g.Wo) % (Idx)g.Ho);
-        const Idx n = m / (Idx)(g.Wo * g.Ho);
+        const Idx m = ste_div<Idx>(i, g.dK), k = i - m * K;
+        const int c = (int)ste_div<Idx>(k, g.dkhkw), tap = (int)(k - (Idx)c * (Idx)(g.kh * g.kw));
+        const int ky = (int)g.dkw.div((uint32_t)tap), kx = tap - ky * g.kw;
+        const Idx n = ste_div<Idx>(m, g.dHoWo), pix = m - n * (Idx)(g.Ho * g.Wo);
+        const int oy = (int)g.dWo.div((uint32_t)pix), ox = (int)pix - oy * g.Wo;
         const int iy = oy * g.sh - g.ph + ky * g.dh, ix = ox * g.sw - g.pw + kx * g.dw;
         float v = 0.0f;
         if (iy >= 0 && iy < g.H && ix >= 0 && ix < g.W) v = x[(((size_t)n * g.C + c) * g.H + iy) * g.W + ix];
@@ -306,22 +318,23 @@ __global__ __launch_bounds__(256) void ste_col2im_kernel(const float *__restrict
         // neighbouring lanes take neighbouring channels of one pixel: their reads of dcol are 4 kh kw bytes apart (one row
         // of dcol serves them all) instead of a whole row apart; the one store and the one read of x per lane are the
         // strided side
-        const int c = (int)(i % (Idx)g.C);
-        const Idx pixel = i / (Idx)g.C;
-        const int ix = (int)(pixel % (Idx)g.W), iy = (int)((pixel / (Idx)g.W) % (Idx)g.H);
-        const Idx n = pixel / (Idx)(g.W * g.H);
+        const Idx pixel = ste_div<Idx>(i, g.dC);
+        const int c = (int)(i - pixel * (Idx)g.C);
+        const Idx n = ste_div<Idx>(pixel, g.dHW);
+        const int pin = (int)(pixel - n * (Idx)(g.H * g.W));
+        const int iy = (int)g.dW.div((uint32_t)pin), ix = pin - iy * g.W;
         const size_t at = (((size_t)n * g.C + c) * g.H + iy) * g.W + ix;
         float s = 0.0f;
         for (int ky = 0; ky < g.kh; ++ky) {
             const int ty = iy + g.ph - ky * g.dh;
-            if (ty < 0 || ty % g.sh) continue;
-            const int oy = ty / g.sh;
-            if (oy >= g.Ho) continue;
+            if (ty < 0) continue;
+            const int oy = (int)g.dsh.div((uint32_t)ty);
+            if (oy * g.sh != ty || oy >= g.Ho) continue;
             for (int kx = 0; kx < g.kw; ++kx) {
                 const int tx = ix + g.pw - kx * g.dw;
-                if (tx < 0 || tx % g.sw) continue;
-                const int ox = tx / g.sw;
-                if (ox >= g.Wo) continue;
+                if (tx < 0) continue;
+                const int ox = (int)g.dsw.div((uint32_t)tx);
+                if (ox * g.sw != tx || ox >= g.Wo) continue;
                 s += dcol[(((size_t)n * g.Ho + oy) * g.Wo + ox) * K + ((size_t)c * g.kh + ky) * g.kw + kx];
             }
         }
