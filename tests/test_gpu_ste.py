@@ -243,3 +243,34 @@ def test_ste_conv2d_refusals(B):
     assert f(ws.data_ptr(), need.value, bits=1) == -1
     assert f(ws.data_ptr(), need.value, g=(2, 3, 2, 2, 4, 5, 5, 1, 1, 0, 0, 1, 1)) == -1       # filter larger than the image
     torch.cuda.synchronize()
+
+
+def test_retraining_loop_of_an_approximate_convolution(B):
+    """The same loop for a 3x3 convolution: forward through the table, straight-through backward over the unfolded input,
+    SGD on the weights; the loss through the approximate layer must fall below a tenth of its start."""
+    from paper_2203_04071_amd import workloads as wl
+    import oracle as orc
+    import torch.nn.functional as F
+    rng = np.random.default_rng(12)
+    N, C, HW, O, bits = 8, 8, 12, 8, 8
+    x = rng.standard_normal((N, C, HW, HW)).astype(np.float32)
+    w_true = (rng.standard_normal((O, C, 3, 3)) * 0.2).astype(np.float32)
+    target = F.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w_true).double(), padding=1).float().cuda()
+    w = dev((w_true + 0.1 * rng.standard_normal(w_true.shape)).astype(np.float32))
+    xd = dev(x)
+    L = B.Lut(wl.make_lut(bits), bits)
+    s_x = orc.scale_from_amax(orc.absmax(x), bits)
+    ws = torch.empty(1 << 24, dtype=torch.uint8, device="cuda")
+    losses = []
+    for it in range(60):
+        s_w = orc.scale_from_amax(float(B.adapt_absmax_f32(w).item()), bits)
+        pw = B.adapt_weights_pack_conv2d(L, B.adapt_quantize_f32(w, s_w, bits))
+        y = B.adapt_conv2d_layer_f32(pw, xd, s_x, np.float32(s_x) * np.float32(s_w), (1, 1), (1, 1))
+        diff = y - target
+        losses.append(float((diff * diff).mean().item()))
+        dy = (diff * (2.0 / diff.numel())).contiguous()
+        _, dw, _ = B.adapt_ste_conv2d_backward_f32(dy, xd, w, (1, 1), (1, 1), (1, 1), s_x, s_w, bits, want=("dw",), workspace=ws)
+        B.adapt_sgd_step_f32(w, dw, 1.0)
+        B.adapt_weights_destroy(pw)
+    assert losses[-1] < 0.1 * losses[0], losses[::10]
+    assert max(losses[1:]) < losses[0], losses              # (near its floor the loss wanders with the rounding; it never blows up)
