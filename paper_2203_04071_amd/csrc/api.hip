@@ -59,6 +59,9 @@ void launch_ste_gemm(const adapt::SteParams &p_in, bool a_t, bool aligned, hipSt
     const int cus = 256;
     const long long t128 = (((long long)p.I + 127) / 128) * (((long long)p.J + 127) / 128);
     int tile = 4 * t128 >= 3 * cus ? 128 : 64;
+    // whole 64-tiles where 128-tiles would be ragged: the unguarded 16-byte loads are worth more than the larger tile
+    const bool whole_ok = aligned && p.R % adapt::STE_TR == 0 && p.lda % 4 == 0 && p.R > 0;
+    if (tile == 128 && whole_ok && (p.I % 128 || p.J % 128) && p.I % 64 == 0 && p.J % 64 == 0) tile = 64;
     if (env_tile == 64 || env_tile == 128) tile = env_tile;
     dim3 grid((unsigned)((p.J + tile - 1) / tile), (unsigned)((p.I + tile - 1) / tile), 1);
     const int chunks = (p.R + adapt::STE_TR - 1) / adapt::STE_TR;
