@@ -404,8 +404,8 @@ int adapt_ste_linear_backward_f32(const float *dy_dev, const float *x_dev, const
  * adapt_approx_conv2d.  dx_dev, dw_dev, db_dev: shapes of x, w and [Cout]; fully overwritten; NULL = not computed; none
  * may alias an input.  workspace_dev: device memory of at least the number of bytes that
  * adapt_ste_conv2d_backward_workspace reports for the same arguments (want_dx / want_dw: whether dx_dev / dw_dev are
- * given), aligned to 256 bytes, owned by the caller, contents undefined afterwards; it holds dy as rows and the unfolded
- * matrices.  fp32 sums (matrix instructions for the products, a fixed tap order for dx).  Asynchronous on `stream`, no
+ * given), aligned to 256 bytes, owned by the caller, contents undefined afterwards; it holds dy as rows, the gradient of
+ * the unfolded input and partial sums (the unfolded input itself is read from x_dev, never written).  fp32 sums (matrix instructions for the products, a fixed tap order for dx).  Asynchronous on `stream`, no
  * allocation.  Errors: ADAPT_ERR_INVALID_ARGUMENT (pointers, geometry, bits, scales, workspace too small or misaligned),
  * ADAPT_ERR_UNSUPPORTED (N Ho Wo above 65535 * 64), ADAPT_ERR_HIP. */
 int adapt_ste_conv2d_backward_workspace(int N, int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w, int pad_h,

@@ -442,7 +442,7 @@ int ste_conv_plan(SteConvPlan *pl, int N, int Cin, int H, int W, int Cout, int k
     pl->rows_bytes = up((size_t)pl->M * Cout * sizeof(float));
     pl->col_bytes = up((size_t)pl->M * (size_t)pl->K * sizeof(float));
     pl->part_bytes = up(STE_PARTIAL_FLOATS * sizeof(float));
-    pl->total = pl->rows_bytes + (want_dw ? pl->col_bytes : 0) + (want_dx ? pl->col_bytes : 0) + pl->part_bytes;
+    pl->total = pl->rows_bytes + (want_dx ? pl->col_bytes : 0) + pl->part_bytes;
     return ADAPT_OK;
 }
 }  // namespace
@@ -492,22 +492,19 @@ int adapt_ste_conv2d_backward_f32(const float *dy_dev, const float *x_dev, const
                     pl.total);
     char *ws = static_cast<char *>(workspace_dev);
     float *rows = reinterpret_cast<float *>(ws);
-    float *col = dw_dev ? reinterpret_cast<float *>(ws + pl.rows_bytes) : nullptr;
-    float *dcol = dx_dev ? reinterpret_cast<float *>(ws + pl.rows_bytes + (dw_dev ? pl.col_bytes : 0)) : nullptr;
+    float *dcol = dx_dev ? reinterpret_cast<float *>(ws + pl.rows_bytes) : nullptr;
     float *partials = reinterpret_cast<float *>(ws + pl.total - pl.part_bytes);      // used by one kernel pair at a time (stream order)
     const int M = (int)pl.M, K = (int)pl.K, P = g.Ho * g.Wo;
-    const size_t rows_n = (size_t)M * Cout, col_n = (size_t)M * K;
+    const size_t rows_n = (size_t)M * Cout, col_n = (size_t)M * K;     // (col_n: elements of dcol)
     if (rows_n < 0x7fffffffull) adapt::ste_rows_from_nchw_kernel<uint32_t><<<ew_grid(rows_n), 256, 0, s>>>(dy_dev, rows, g, rows_n);
     else adapt::ste_rows_from_nchw_kernel<size_t><<<ew_grid(rows_n), 256, 0, s>>>(dy_dev, rows, g, rows_n);
     HIP_TRY(hipGetLastError());
-    if (dw_dev) {           // dw [Cout][K] = inside(w) * rows^T [Cout][M] . fq(col(x)) [M][K]
-        if (col_n < 0x7fffffffull) adapt::ste_im2col_kernel<uint32_t><<<ew_grid(col_n), 256, 0, s>>>(x_dev, col, g, col_n);
-        else adapt::ste_im2col_kernel<size_t><<<ew_grid(col_n), 256, 0, s>>>(x_dev, col, g, col_n);
-        HIP_TRY(hipGetLastError());
+    if (dw_dev) {           // dw [Cout][K] = inside(w) * rows^T [Cout][M] . fq(col(x)) [M][K], col(x) read from x itself
         adapt::SteParams p{};
-        p.a = rows; p.b = col; p.o = w_dev; p.c = dw_dev;
+        p.a = rows; p.b = x_dev; p.o = w_dev; p.c = dw_dev;
         p.I = Cout; p.J = K; p.R = M; p.lda = Cout;
         p.sb = s_x; p.so = s_w; p.Q = Q;
+        p.im2col = 1; p.g = g;
         launch_ste_gemm(p, true, true, s, partials);        // (both operands lie in the workspace)
         HIP_TRY(hipGetLastError());
     }

@@ -22,6 +22,19 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 constexpr int STE_TR = 32;          // contraction indices per staged chunk
 constexpr int STE_THREADS = 256;    // four waves, 2 x 2 over the workgroup's output tile (x KS, see the kernel)
 
+// geometry of a convolution whose unfolded input takes part in a product (see the end of this file)
+struct SteConvGeo {
+    int N, C, H, W, O, kh, kw, sh, sw, ph, pw, dh, dw, Ho, Wo;
+    FastDiv dK, dkw, dkhkw, dWo, dHoWo, dC, dW, dHW, dO, dP, dsh, dsw;      // the divisors of the index decodes below
+};
+
+// n / f.d: multiply-and-shift for 32-bit indices (exact below 2^31), a plain division otherwise
+template <typename Idx>
+__device__ __forceinline__ Idx ste_div(Idx n, const FastDiv &f) {
+    if constexpr (sizeof(Idx) == 4) return (Idx)f.div((uint32_t)n);
+    else return n / (Idx)f.d;
+}
+
 // c[i][j] = inside(o[i][j]) * sum_r A(i, r) * fq(b[r][j])
 struct SteParams {
     const float *a;     // A_T: element (i, r) at a[r * lda + i]; else at a[i * lda + r]
@@ -31,6 +44,8 @@ struct SteParams {
     int I, J, R, lda;
     float sb, so, Q;
     int cps;            // chunks of STE_TR contraction indices per grid z: z > 0 writes its partial sums to c + z * I * J
+    int im2col;         // b is an NCHW image tensor x and stands for its unfolded matrix: b[r][j] = x(n, c, oy s - p + ky d, ...)
+    SteConvGeo g;       //   with r = (n, oy, ox), j = (c, ky, kx) of this geometry, zero outside the image
 };
 
 __device__ __forceinline__ float ste_fake_quant(float x, float s, float Q) {
@@ -61,6 +76,29 @@ __device__ __forceinline__ float4 ste_load4(const float *__restrict__ base, int 
     v.z = (in_row && col + 2 < cols) ? v.z : 0.0f;
     v.w = (in_row && col + 3 < cols) ? v.w : 0.0f;
     return v;
+}
+
+// Four consecutive elements of a row of the unfolded input of a convolution, read from the image itself (row = (n, oy, ox),
+// col = (c, ky, kx), a multiple of 4): no unfolded copy exists.  Branch-free like the ragged loads above: the address of
+// an element outside the matrix or the image is replaced by 0 and the value by zero.
+__device__ __forceinline__ float4 ste_load4_unfolded(const float *__restrict__ x, int row, int col, int rows, int cols, const SteConvGeo &g) {
+    const uint32_t m = (uint32_t)min(row, rows - 1);
+    const uint32_t n = g.dHoWo.div(m), pix = m - n * (uint32_t)(g.Ho * g.Wo);
+    const int oy = (int)g.dWo.div(pix), ox = (int)pix - oy * g.Wo;
+    const int y0 = oy * g.sh - g.ph, x0 = ox * g.sw - g.pw;
+    float v[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t k = (uint32_t)min(col + q, cols - 1);
+        const uint32_t c = g.dkhkw.div(k), tap = k - c * (uint32_t)(g.kh * g.kw);
+        const int ky = (int)g.dkw.div(tap), kx = (int)tap - ky * g.kw;
+        const int iy = y0 + ky * g.dh, ix = x0 + kx * g.dw;
+        const bool ok = row < rows && col + q < cols && iy >= 0 && iy < g.H && ix >= 0 && ix < g.W;
+        const size_t at = ok ? (((size_t)n * g.C + c) * g.H + iy) * g.W + ix : 0;
+        const float t = x[at];
+        v[q] = ok ? t : 0.0f;
+    }
+    return make_float4(v[0], v[1], v[2], v[3]);
 }
 
 // TILE x TILE outputs per workgroup (128: four 32 x 32 blocks per wave; 64: one), FULL as above.  Chunks of 32
@@ -98,7 +136,8 @@ __global__ __launch_bounds__(STE_THREADS * KS) void ste_gemm_kernel(SteParams p)
 #pragma unroll
         for (int pass = 0; pass < PASSES; ++pass) {
             const int r = tid / TPR + RPP * pass, c4 = (tid % TPR) * 4;
-            rb[pass] = ste_load4<FULL>(p.b, r0 + r, j0 + c4, p.R, p.J, p.J);
+            if (p.im2col) rb[pass] = ste_load4_unfolded(p.b, r0 + r, j0 + c4, p.R, p.J, p.g);
+            else rb[pass] = ste_load4<FULL>(p.b, r0 + r, j0 + c4, p.R, p.J, p.J);
             if (A_T) {
                 ra[pass] = ste_load4<FULL>(p.a, r0 + r, i0 + c4, p.R, p.I, p.lda);
             } else {
@@ -266,19 +305,8 @@ __global__ __launch_bounds__(STE_COLSUM_THREADS) void ste_colsum_kernel(const fl
 // ---- convolution (groups = 1): the same two products over the unfolded input --------------------------------------
 // y[m][o] = sum_k col(x^)[m][k] * w^[o][k] with m = (n, oy, ox), k = (c, ky, kx) (Sec. III-B: the convolution as a matrix
 // product over the unfolded input), so dw = mask(w) . dy_rows^T . fq(col(x)) and dcol = dy_rows . fq(w), and dx gathers
-// dcol back onto the image (a fixed order) under mask(x).  The unfolded matrices live in a workspace of the caller.
-struct SteConvGeo {
-    int N, C, H, W, O, kh, kw, sh, sw, ph, pw, dh, dw, Ho, Wo;
-    FastDiv dK, dkw, dkhkw, dWo, dHoWo, dC, dW, dHW, dO, dP, dsh, dsw;      // the divisors of the index decodes below
-};
-
-// n / f.d: multiply-and-shift for 32-bit indices (exact below 2^31), a plain division otherwise
-template <typename Idx>
-__device__ __forceinline__ Idx ste_div(Idx n, const FastDiv &f) {
-    if constexpr (sizeof(Idx) == 4) return (Idx)f.div((uint32_t)n);
-    else return n / (Idx)f.d;
-}
-
+// dcol back onto the image (a fixed order) under mask(x).  col(x) is never written: the product reads it from the image
+// (ste_load4_unfolded); dy as rows, dcol and the partial sums live in a workspace of the caller.
 // dy [N][O][P] -> rows [N * P][O]
 template <typename Idx>
 __global__ __launch_bounds__(256) void ste_rows_from_nchw_kernel(const float *__restrict__ dy, float *__restrict__ rows, SteConvGeo g, size_t total) {
@@ -287,24 +315,6 @@ __global__ __launch_bounds__(256) void ste_rows_from_nchw_kernel(const float *__
     for (Idx i = (Idx)blockIdx.x * 256 + threadIdx.x; i < (Idx)total; i += stride) {
         const Idx m = ste_div<Idx>(i, g.dO), o = i - m * (Idx)O, n = ste_div<Idx>(m, g.dP), pix = m - n * (Idx)P;
         rows[i] = dy[((size_t)n * O + o) * P + pix];
-    }
-}
-
-// x [N][C][H][W] -> col [N * Ho * Wo][C * kh * kw], zero where a tap lies outside the image
-template <typename Idx>
-__global__ __launch_bounds__(256) void ste_im2col_kernel(const float *__restrict__ x, float *__restrict__ col, SteConvGeo g, size_t total) {
-    const Idx stride = (Idx)gridDim.x * 256;
-    const Idx K = (Idx)g.C * g.kh * g.kw;
-    for (Idx i = (Idx)blockIdx.x * 256 + threadIdx.x; i < (Idx)total; i += stride) {
-        const Idx m = ste_div<Idx>(i, g.dK), k = i - m * K;
-        const int c = (int)ste_div<Idx>(k, g.dkhkw), tap = (int)(k - (Idx)c * (Idx)(g.kh * g.kw));
-        const int ky = (int)g.dkw.div((uint32_t)tap), kx = tap - ky * g.kw;
-        const Idx n = ste_div<Idx>(m, g.dHoWo), pix = m - n * (Idx)(g.Ho * g.Wo);
-        const int oy = (int)g.dWo.div((uint32_t)pix), ox = (int)pix - oy * g.Wo;
-        const int iy = oy * g.sh - g.ph + ky * g.dh, ix = ox * g.sw - g.pw + kx * g.dw;
-        float v = 0.0f;
-        if (iy >= 0 && iy < g.H && ix >= 0 && ix < g.W) v = x[(((size_t)n * g.C + c) * g.H + iy) * g.W + ix];
-        col[i] = v;
     }
 }
 
