@@ -414,7 +414,7 @@ adapt::FastDiv fast_div(uint32_t d);
 struct SteConvPlan {
     adapt::SteConvGeo g;
     long long M, K;
-    size_t rows_bytes, col_bytes, part_bytes, total;
+    size_t rows_bytes, col_bytes, wp_bytes, part_bytes, total;
 };
 int ste_conv_plan(SteConvPlan *pl, int N, int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w, int pad_h, int pad_w,
                   int dil_h, int dil_w, bool want_dx, bool want_dw, const char *who) {
@@ -442,7 +442,8 @@ int ste_conv_plan(SteConvPlan *pl, int N, int Cin, int H, int W, int Cout, int k
     pl->rows_bytes = up((size_t)pl->M * Cout * sizeof(float));
     pl->col_bytes = up((size_t)pl->M * (size_t)pl->K * sizeof(float));
     pl->part_bytes = up(STE_PARTIAL_FLOATS * sizeof(float));
-    pl->total = pl->rows_bytes + (want_dx ? pl->col_bytes : 0) + pl->part_bytes;
+    pl->wp_bytes = want_dx ? up((size_t)Cout * (size_t)pl->K * sizeof(float)) : 0;
+    pl->total = pl->rows_bytes + (want_dx ? pl->col_bytes : 0) + pl->wp_bytes + pl->part_bytes;
     return ADAPT_OK;
 }
 }  // namespace
@@ -510,10 +511,13 @@ int adapt_ste_conv2d_backward_f32(const float *dy_dev, const float *x_dev, const
     }
     if (dx_dev) {           // dcol [M][K] = rows [M][Cout] . fq(w) [Cout][K]; dx = inside(x) * the taps of dcol gathered onto the image
         adapt::SteParams p{};
-        p.a = rows; p.b = w_dev; p.o = nullptr; p.c = dcol;
+        float *wp = reinterpret_cast<float *>(ws + pl.rows_bytes + pl.col_bytes);      // the weights with the channel last in each row
+        adapt::ste_taps_first_kernel<<<ew_grid(w_elems), 256, 0, s>>>(w_dev, wp, Cout, Cin, kh * kw);
+        HIP_TRY(hipGetLastError());
+        p.a = rows; p.b = wp; p.o = nullptr; p.c = dcol;
         p.I = M; p.J = K; p.R = Cout; p.lda = Cout;
         p.sb = s_w; p.so = 1.0f; p.Q = Q;
-        launch_ste_gemm(p, false, aligned16(w_dev), s);
+        launch_ste_gemm(p, false, true, s);
         HIP_TRY(hipGetLastError());
         if (x_elems < 0x7fffffffull && col_n < 0x7fffffffull)
             adapt::ste_col2im_kernel<uint32_t><<<ew_grid(x_elems), 256, 0, s>>>(dcol, x_dev, dx_dev, g, s_x, Q, x_elems);

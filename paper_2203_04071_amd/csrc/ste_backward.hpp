@@ -318,16 +318,25 @@ __global__ __launch_bounds__(256) void ste_rows_from_nchw_kernel(const float *__
     }
 }
 
-// dx[n][c][iy][ix] = inside(x) * sum over the taps (ky, kx ascending) that land on (iy, ix) of dcol[(n, oy, ox)][(c, ky, kx)]
+// w [O][C][T] -> wp [O][T][C] (T = kh kw taps): with the channel last in dcol's columns, the lanes of the gather kernel
+// below, which run along channels, read consecutive floats
+__global__ __launch_bounds__(256) void ste_taps_first_kernel(const float *__restrict__ w, float *__restrict__ wp, int O, int C, int T) {
+    const size_t total = (size_t)O * C * T, stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += stride) {
+        const size_t o = i / ((size_t)C * T), rem = i - o * (size_t)C * T, t = rem / C, c = rem - t * C;
+        wp[i] = w[(o * C + c) * T + t];
+    }
+}
+
+// dx[n][c][iy][ix] = inside(x) * sum over the taps (ky, kx ascending) that land on (iy, ix) of dcol[(n, oy, ox)][(ky, kx, c)]
 template <typename Idx>
 __global__ __launch_bounds__(256) void ste_col2im_kernel(const float *__restrict__ dcol, const float *__restrict__ x, float *__restrict__ dx,
                                                          SteConvGeo g, float s_x, float Q, size_t total) {
     const Idx stride = (Idx)gridDim.x * 256;
     const size_t K = (size_t)g.C * g.kh * g.kw;
     for (Idx i = (Idx)blockIdx.x * 256 + threadIdx.x; i < (Idx)total; i += stride) {
-        // neighbouring lanes take neighbouring channels of one pixel: their reads of dcol are 4 kh kw bytes apart (one row
-        // of dcol serves them all) instead of a whole row apart; the one store and the one read of x per lane are the
-        // strided side
+        // neighbouring lanes take neighbouring channels of one pixel: their reads of dcol are consecutive floats of one
+        // row; the one store and the one read of x per lane are the strided side
         const Idx pixel = ste_div<Idx>(i, g.dC);
         const int c = (int)(i - pixel * (Idx)g.C);
         const Idx n = ste_div<Idx>(pixel, g.dHW);
@@ -345,7 +354,7 @@ __global__ __launch_bounds__(256) void ste_col2im_kernel(const float *__restrict
                 if (tx < 0) continue;
                 const int ox = (int)g.dsw.div((uint32_t)tx);
                 if (ox * g.sw != tx || ox >= g.Wo) continue;
-                s += dcol[(((size_t)n * g.Ho + oy) * g.Wo + ox) * K + ((size_t)c * g.kh + ky) * g.kw + kx];
+                s += dcol[(((size_t)n * g.Ho + oy) * g.Wo + ox) * K + (size_t)(ky * g.kw + kx) * g.C + c];
             }
         }
         dx[at] = ste_inside(x[at], s_x, Q) ? s : 0.0f;
