@@ -8,6 +8,9 @@ configurations).  Default workload: the 3x3 convolution layer the metric is quot
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1|2|3|4|5] [--bits B] [--no-cpu-baseline]
                   [--copy-calibration]
+
+Configurations 6 - 11 are workloads beyond the five baseline ones (separable block, GRU, 12-bit operands, the
+straight-through backward pass of a linear and of a convolution layer); they print the same line with their own metric.
 """
 from __future__ import annotations
 

@@ -199,6 +199,9 @@ CONV_CASES = [
 
 @pytest.mark.parametrize("case", CONV_CASES)
 def test_ste_conv2d_backward_matches_oracle(B, case):
+    """Same bar as the linear layer.  dw and db are fp32 sums of M = N Ho Wo terms in some fixed order (split into partial
+    sums for small outputs): gamma(M + 1).  An element of dx is a sum of at most kh kw fp32 dot products of length Cout:
+    gamma(Cout + kh kw + 1).  Both against the sums of absolute terms, which the oracle forms the same way."""
     N, C, H, W, O, kh, kw, stride, pad, dil, bits = case
     rng = np.random.default_rng(sum(case[:7]) + bits)
     x = rng.standard_normal((N, C, H, W)).astype(np.float32)
