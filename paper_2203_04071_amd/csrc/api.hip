@@ -68,7 +68,7 @@ void launch_ste_gemm(const adapt::SteParams &p_in, bool a_t, bool aligned, hipSt
     const long long tiles = (long long)grid.x * grid.y;
     p.cps = chunks > 0 ? chunks : 1;
     int parts = 1;
-    if (partials && tile == 64 && tiles < cus && chunks >= 8) {
+    if (partials && p.im2col && tile == 64 && tiles < cus && chunks >= 8) {       // (the kernels split only in their unfolded-input form)
         int want = (int)((2 * cus + tiles - 1) / tiles);
         if (want > chunks / 4) want = chunks / 4;                   // at least four chunks per part
         if (want >= 2) {
@@ -80,12 +80,13 @@ void launch_ste_gemm(const adapt::SteParams &p_in, bool a_t, bool aligned, hipSt
     int ks = tiles * parts < 2 * cus ? 2 : 1;
     if (env_ks == 1 || env_ks == 2) ks = env_ks;
     const bool full = aligned && p.I % tile == 0 && p.J % tile == 0 && p.R % adapt::STE_TR == 0 && p.lda % 4 == 0 && p.R > 0;
-#define STE_LAUNCH4(AT, T, F) \
-    do { if (ks == 2) adapt::ste_gemm_kernel<AT, T, F, 2><<<grid, adapt::STE_THREADS * 2, 0, s>>>(p); \
-         else adapt::ste_gemm_kernel<AT, T, F, 1><<<grid, adapt::STE_THREADS, 0, s>>>(p); } while (0)
-#define STE_LAUNCH2(AT, T) do { if (full) STE_LAUNCH4(AT, T, true); else STE_LAUNCH4(AT, T, false); } while (0)
-    if (a_t) { if (tile == 128) STE_LAUNCH2(true, 128); else STE_LAUNCH2(true, 64); }
-    else { if (tile == 128) STE_LAUNCH2(false, 128); else STE_LAUNCH2(false, 64); }
+#define STE_LAUNCH4(AT, T, F, U) \
+    do { if (ks == 2) adapt::ste_gemm_kernel<AT, T, F, 2, U><<<grid, adapt::STE_THREADS * 2, 0, s>>>(p); \
+         else adapt::ste_gemm_kernel<AT, T, F, 1, U><<<grid, adapt::STE_THREADS, 0, s>>>(p); } while (0)
+#define STE_LAUNCH2(AT, T, U) do { if (full) STE_LAUNCH4(AT, T, true, U); else STE_LAUNCH4(AT, T, false, U); } while (0)
+    if (a_t && p.im2col) { if (tile == 128) STE_LAUNCH2(true, 128, true); else STE_LAUNCH2(true, 64, true); }
+    else if (a_t) { if (tile == 128) STE_LAUNCH2(true, 128, false); else STE_LAUNCH2(true, 64, false); }
+    else { if (tile == 128) STE_LAUNCH2(false, 128, false); else STE_LAUNCH2(false, 64, false); }
 #undef STE_LAUNCH2
 #undef STE_LAUNCH4
     if (parts > 1) {

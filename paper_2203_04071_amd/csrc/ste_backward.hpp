@@ -107,7 +107,9 @@ __device__ __forceinline__ float4 ste_load4_unfolded(const float *__restrict__ x
 // KS = 2: eight waves; waves w and w + 4 share an output quarter and take alternate pairs of contraction indices, their
 // sums are added through LDS at the end (a fixed order).  For launches with about one workgroup per compute unit:
 // two waves per SIMD, so that one wave's staging arithmetic runs under the other's matrix instructions.
-template <bool A_T, int TILE, bool FULL, int KS>
+// UNFOLD: b is an image tensor that stands for its unfolded matrix (p.im2col; a template parameter so that the plain
+// products carry no trace of it: a run-time branch around the loads cost them 10 - 30 %).
+template <bool A_T, int TILE, bool FULL, int KS, bool UNFOLD = false>
 __global__ __launch_bounds__(STE_THREADS * KS) void ste_gemm_kernel(SteParams p) {
     constexpr int THREADS = STE_THREADS * KS;
     constexpr int LDB = TILE + 4;                   // LDS row length in floats: 16-byte rows, shifted by 4 banks per row
@@ -136,7 +138,7 @@ __global__ __launch_bounds__(STE_THREADS * KS) void ste_gemm_kernel(SteParams p)
 #pragma unroll
         for (int pass = 0; pass < PASSES; ++pass) {
             const int r = tid / TPR + RPP * pass, c4 = (tid % TPR) * 4;
-            if (p.im2col) rb[pass] = ste_load4_unfolded(p.b, r0 + r, j0 + c4, p.R, p.J, p.g);
+            if constexpr (UNFOLD) rb[pass] = ste_load4_unfolded(p.b, r0 + r, j0 + c4, p.R, p.J, p.g);
             else rb[pass] = ste_load4<FULL>(p.b, r0 + r, j0 + c4, p.R, p.J, p.J);
             if (A_T) {
                 ra[pass] = ste_load4<FULL>(p.a, r0 + r, i0 + c4, p.R, p.I, p.lda);
@@ -168,9 +170,10 @@ __global__ __launch_bounds__(STE_THREADS * KS) void ste_gemm_kernel(SteParams p)
         }
     };
 
-    const int ch0 = blockIdx.z * p.cps;             // this workgroup's share of the contraction
-    const int chunks = max(0, min((p.R + STE_TR - 1) / STE_TR, ch0 + p.cps) - ch0);
-    float *const cout = p.c + (size_t)blockIdx.z * (size_t)p.I * (size_t)p.J;
+    // this workgroup's share of the contraction (only the products over an unfolded input are ever split over grid z)
+    const int ch0 = UNFOLD ? blockIdx.z * p.cps : 0;
+    const int chunks = UNFOLD ? max(0, min((p.R + STE_TR - 1) / STE_TR, ch0 + p.cps) - ch0) : (p.R + STE_TR - 1) / STE_TR;
+    float *const cout = UNFOLD ? p.c + (size_t)blockIdx.z * (size_t)p.I * (size_t)p.J : p.c;
     if (chunks > 0) { fetch(ch0 * STE_TR); stash(0); }
     __syncthreads();
     for (int ch = 0; ch < chunks; ++ch) {
