@@ -126,3 +126,10 @@ def ste_conv2d_backward(dy, x, w, stride, pad, dil, s_x, s_w, bits, absolute=Fal
         dx = dx * clip_inside(x32, s_x, bits)
         dwt = dwt * clip_inside(w32, s_w, bits)
     return dx, dwt, db
+
+
+def relu_backward(dy, y) -> np.ndarray:
+    """Gradient through y = max(v, 0), the activation the approximate layers fuse: dy where y > 0, else 0 (fp32, exact)."""
+    dy = np.asarray(dy, dtype=np.float32)
+    y = np.asarray(y, dtype=np.float32)
+    return np.where(y > 0, dy, np.float32(0)).astype(np.float32)

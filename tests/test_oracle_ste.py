@@ -149,3 +149,14 @@ def test_conv_backward_of_a_1x1_convolution_is_the_linear_backward():
     np.testing.assert_allclose(rows(dx), lx, rtol=1e-13, atol=1e-15)
     np.testing.assert_allclose(dw.reshape(O, C), lw, rtol=1e-13, atol=1e-15)
     np.testing.assert_allclose(db, lb, rtol=1e-13)
+
+
+def test_relu_backward_equals_autograd():
+    v = np.array([-2.0, -0.0, 0.0, 1e-30, 3.0, np.nan], dtype=np.float32)
+    dy = np.array([1.0, 2.0, 3.0, 4.0, 5.0, 6.0], dtype=np.float32)
+    t = torch.tensor(v[:5], requires_grad=True)
+    y = torch.relu(t)
+    (y * torch.tensor(dy[:5])).sum().backward()
+    got = ste.relu_backward(dy, np.maximum(v, 0))
+    np.testing.assert_array_equal(got[:5], t.grad.numpy())
+    np.testing.assert_array_equal(got[:5], [0, 0, 0, 4, 5])
