@@ -415,6 +415,11 @@ int adapt_ste_conv2d_backward_f32(const float *dy_dev, const float *x_dev, const
                                   float s_w, int bits, float *dx_dev, float *dw_dev, float *db_dev, void *workspace_dev,
                                   size_t workspace_bytes, void *stream);
 
+/* Gradient through the ReLU that the layer calls fuse (act = 1), for the backward pass of Sec. III-A's retraining:
+ * dx[i] = y[i] > 0 ? dy[i] : 0, y being the layer's output.  n floats each on the device; dx_dev may be dy_dev (in place).
+ * Asynchronous on `stream`.  Errors: ADAPT_ERR_INVALID_ARGUMENT (NULL pointer), ADAPT_ERR_HIP. */
+int adapt_relu_backward_f32(const float *dy_dev, const float *y_dev, float *dx_dev, size_t n, void *stream);
+
 /* One plain stochastic-gradient step, the optimiser the paper retrains with (Sec. IV-A, "Quantization and retraining":
  * SGD, learning rate 1e-4): w[i] <- w[i] - lr * g[i] in fp32, the product and the difference rounded separately.
  * w_dev, g_dev: n floats each on the device, distinct; in place on w_dev.  Asynchronous on `stream`.

@@ -36,7 +36,7 @@ EXPORTS = [
     "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32", "adapt_lstm_cell_q_f32", "adapt_lstm_step_f32", "adapt_gru_step_f32", "adapt_rnn_step_f32", "adapt_gru_cell_f32", "adapt_rnn_cell_f32",
     "adapt_lut16_create", "adapt_lut16_create_from_func", "adapt_lut16_destroy", "adapt_lut16_bits", "adapt_quantize_i16_f32",
     "adapt_approx_linear_i16", "adapt_approx_conv2d_i16", "adapt_approx_linear_func_i16", "adapt_approx_conv2d_func_i16",
-    "adapt_ste_linear_backward_f32", "adapt_sgd_step_f32", "adapt_ste_conv2d_backward_workspace", "adapt_ste_conv2d_backward_f32",
+    "adapt_ste_linear_backward_f32", "adapt_sgd_step_f32", "adapt_relu_backward_f32", "adapt_ste_conv2d_backward_workspace", "adapt_ste_conv2d_backward_f32",
 ]
 
 
@@ -116,6 +116,7 @@ def load() -> ctypes.CDLL:
     L.adapt_gru_cell_f32.argtypes = [vp, vp, f32, f32, vp, vp, vp, vp, vp, f32, i32, i32, i32, vp]
     L.adapt_rnn_cell_f32.argtypes = [vp, vp, f32, f32, vp, i32, vp, vp, f32, i32, i32, i32, vp]
     L.adapt_sgd_step_f32.argtypes = [vp, vp, sz, f32, vp]
+    L.adapt_relu_backward_f32.argtypes = [vp, vp, vp, sz, vp]
     L.adapt_ste_conv2d_backward_workspace.argtypes = [i32] * 15 + [ctypes.POINTER(sz)]
     L.adapt_ste_conv2d_backward_f32.argtypes = [vp, vp, vp] + [i32] * 13 + [f32, f32, i32, vp, vp, vp, vp, sz, vp]
     L.adapt_ste_linear_backward_f32.argtypes = [vp, vp, vp, i32, i32, i32, f32, f32, i32, vp, vp, vp, vp]
@@ -754,3 +755,12 @@ def adapt_ste_conv2d_backward_f32(dy, x, w, stride, pad, dil, s_x, s_w, bits, wa
                                               _ptr(db, torch.float32), ctypes.c_void_p(workspace.data_ptr()), workspace.numel(),
                                               _stream(stream)))
     return dx, dw, db
+
+
+def adapt_relu_backward_f32(dy, y, out=None, stream=None):
+    """dy where y > 0, else 0 (out may be dy)."""
+    assert dy.shape == y.shape
+    if out is None:
+        out = torch.empty_like(dy)
+    _chk(load().adapt_relu_backward_f32(_ptr(dy, torch.float32), _ptr(y, torch.float32), _ptr(out, torch.float32), dy.numel(), _stream(stream)))
+    return out

@@ -2258,6 +2258,14 @@ int adapt_add_f32(const float *a_dev, const float *b_dev, float *y_dev, size_t n
     return ADAPT_OK;
 }
 
+int adapt_relu_backward_f32(const float *dy_dev, const float *y_dev, float *dx_dev, size_t n, void *stream) {
+    if ((!dy_dev || !y_dev || !dx_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_relu_backward_f32: NULL pointer");
+    if (!n) return ADAPT_OK;
+    adapt::relu_backward_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(dy_dev, y_dev, dx_dev, n);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
+}
+
 int adapt_sgd_step_f32(float *w_dev, const float *g_dev, size_t n, float lr, void *stream) {
     if ((!w_dev || !g_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_sgd_step_f32: NULL pointer");
     if (w_dev == g_dev && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_sgd_step_f32: w_dev and g_dev must differ");

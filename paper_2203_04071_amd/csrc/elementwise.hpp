@@ -255,6 +255,12 @@ __global__ __launch_bounds__(EW_THREADS) void add_kernel(const float *a, const f
     }
 }
 
+// gradient through the fused ReLU: dx = dy where the layer's output y is positive
+__global__ __launch_bounds__(EW_THREADS) void relu_backward_kernel(const float *__restrict__ dy, const float *__restrict__ y, float *__restrict__ dx, size_t n) {
+    const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) dx[i] = y[i] > 0.0f ? dy[i] : 0.0f;
+}
+
 // plain stochastic-gradient step of the retraining loop: w <- w - lr * g, the product and the difference rounded separately
 __global__ __launch_bounds__(EW_THREADS) void sgd_kernel(float *__restrict__ w, const float *__restrict__ g, size_t n, float lr) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;

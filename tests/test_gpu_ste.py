@@ -277,3 +277,18 @@ def test_retraining_loop_of_an_approximate_convolution(B):
         B.adapt_weights_destroy(pw)
     assert losses[-1] < 0.1 * losses[0], losses[::10]
     assert max(losses[1:]) < losses[0], losses              # (near its floor the loss wanders with the rounding; it never blows up)
+
+
+@pytest.mark.parametrize("n", [0, 1, 1000, (1 << 20) + 3])
+def test_relu_backward_bit_exact(B, n):
+    rng = np.random.default_rng(n + 5)
+    y = np.maximum(rng.standard_normal(n), 0).astype(np.float32)
+    dy = rng.standard_normal(n).astype(np.float32)
+    if n >= 4:
+        y[:4] = [0.0, -0.0, 1e-38, np.nan]
+    want = ste.relu_backward(dy, y)
+    got = B.adapt_relu_backward_f32(dev(dy), dev(y))
+    assert (got.cpu().numpy().view(np.uint32) == want.view(np.uint32)).all()
+    d = dev(dy)
+    B.adapt_relu_backward_f32(d, dev(y), out=d)             # in place
+    assert (d.cpu().numpy().view(np.uint32) == want.view(np.uint32)).all()
