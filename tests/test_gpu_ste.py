@@ -292,3 +292,42 @@ def test_relu_backward_bit_exact(B, n):
     d = dev(dy)
     B.adapt_relu_backward_f32(d, dev(y), out=d)             # in place
     assert (d.cpu().numpy().view(np.uint32) == want.view(np.uint32)).all()
+
+
+def test_retraining_loop_of_two_approximate_layers(B):
+    """linear -> ReLU -> linear, both through the table: the second layer's input gradient goes through the ReLU gradient
+    into the first layer's weight gradient, so the loop only converges if dx is a useful gradient too."""
+    from paper_2203_04071_amd import workloads as wl
+    import oracle as orc
+    rng = np.random.default_rng(13)
+    M, K1, Hd, N, bits = 256, 32, 48, 16, 8
+    Q = (1 << (bits - 1)) - 1
+    x = rng.standard_normal((M, K1)).astype(np.float32)
+    w1_true = (rng.standard_normal((Hd, K1)) * 0.3).astype(np.float32)
+    w2_true = (rng.standard_normal((N, Hd)) * 0.3).astype(np.float32)
+    target = dev((np.maximum(x.astype(np.float64) @ w1_true.T, 0) @ w2_true.T).astype(np.float32))
+    w1 = dev((w1_true + 0.08 * rng.standard_normal(w1_true.shape)).astype(np.float32))
+    w2 = dev((w2_true + 0.08 * rng.standard_normal(w2_true.shape)).astype(np.float32))
+    xd = dev(x)
+    L = B.Lut(wl.make_lut(bits), bits)
+    s_x = orc.scale_from_amax(orc.absmax(x), bits)
+    scale = lambda t: orc.scale_from_amax(float(B.adapt_absmax_f32(t).item()), bits)
+    losses = []
+    for it in range(80):
+        s_w1, s_w2 = scale(w1), scale(w2)
+        p1 = B.adapt_weights_pack_linear(L, B.adapt_quantize_f32(w1, s_w1, bits))
+        p2 = B.adapt_weights_pack_linear(L, B.adapt_quantize_f32(w2, s_w2, bits))
+        h = B.adapt_linear_layer_f32(p1, xd, s_x, np.float32(s_x) * np.float32(s_w1), act=B.ACT_RELU)
+        s_h = scale(h)
+        y = B.adapt_linear_layer_f32(p2, h, s_h, np.float32(s_h) * np.float32(s_w2))
+        diff = y - target
+        losses.append(float((diff * diff).mean().item()))
+        dy = (diff * (2.0 / diff.numel())).contiguous()
+        dh, dw2, _ = B.adapt_ste_linear_backward_f32(dy, h, w2, s_h, s_w2, bits, want=("dx", "dw"))
+        B.adapt_relu_backward_f32(dh, h, out=dh)
+        _, dw1, _ = B.adapt_ste_linear_backward_f32(dh, xd, w1, s_x, s_w1, bits, want=("dw",))
+        B.adapt_sgd_step_f32(w1, dw1, 0.5)
+        B.adapt_sgd_step_f32(w2, dw2, 0.5)
+        B.adapt_weights_destroy(p1); B.adapt_weights_destroy(p2)
+    assert np.isfinite(losses).all()
+    assert losses[-1] < 0.3 * losses[0], losses[::10]
