@@ -1,164 +1,15 @@
-// C ABI of the library: argument checks, table handles, launch geometry.  All arithmetic of the
-// path runs in the kernels included below; nothing here falls back to host computation.
-#include <hip/hip_runtime.h>
-
-#include <cstdarg>
-#include <cstdio>
-#include <cstring>
-#include <new>
-#include <vector>
-
-#include "../../include/adapt_mi355.h"
-#include "elementwise.hpp"
+// C ABI, part 2: the table-lookup products (linear, convolution, transposed convolution), packed weights, whole-layer
+// calls, chained layers and recurrent time steps.  All arithmetic of the path runs in the kernels included below;
+// nothing here falls back to host computation.
+#include "api_common.hpp"
 #include "lut_lines.hpp"
 #include "lut_wide.hpp"
 #include "lut_rows.hpp"
 #include "lut_grouped.hpp"
-#include "lut_big.hpp"
-#include "ste_backward.hpp"
+
+using namespace adapt_api;
 
 namespace {
-
-thread_local char g_err[512] = "";
-
-int fail(int code, const char *fmt, ...) {
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(g_err, sizeof(g_err), fmt, ap);
-    va_end(ap);
-    return code;
-}
-
-#define HIP_TRY(expr)                                                                                  \
-    do {                                                                                               \
-        hipError_t e_ = (expr);                                                                        \
-        if (e_ != hipSuccess)                                                                          \
-            return fail(e_ == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "%s: %s", \
-                        #expr, hipGetErrorString(e_));                                                 \
-    } while (0)
-
-inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
-// Shape of the gradient products' launch: 128 x 128 outputs per workgroup where that still occupies three quarters of
-// the compute units, else 64 x 64; eight waves per workgroup instead of four (KS = 2) where there are fewer than two
-// workgroups per compute unit.  Env ADAPT_STE_TILE = 64 / 128 and ADAPT_STE_KS = 1 / 2 force one (for measurements).
-// `full`: whole tiles, 16-byte rows.
-int ste_env(const char *name) {
-    const char *e = getenv(name);
-    return e ? atoi(e) : 0;
-}
-// Floats of partial sums a split product may need: it is split only below 256 tiles of 64 x 64, into at most
-// 512 / tiles + 1 parts.
-constexpr size_t STE_PARTIAL_FLOATS = (size_t)(512 + 256) * 64 * 64;
-
-// partials != nullptr (STE_PARTIAL_FLOATS floats): a product with few output tiles and a long contraction is split
-// over grid z into partial sums, which ste_reduce_masked_kernel adds in a fixed order.
-void launch_ste_gemm(const adapt::SteParams &p_in, bool a_t, bool aligned, hipStream_t s, float *partials = nullptr) {
-    static const int env_tile = ste_env("ADAPT_STE_TILE"), env_ks = ste_env("ADAPT_STE_KS");
-    adapt::SteParams p = p_in;
-    const int cus = 256;
-    const long long t128 = (((long long)p.I + 127) / 128) * (((long long)p.J + 127) / 128);
-    int tile = 4 * t128 >= 3 * cus ? 128 : 64;
-    // whole 64-tiles where 128-tiles would be ragged: the unguarded 16-byte loads are worth more than the larger tile
-    const bool whole_ok = aligned && p.R % adapt::STE_TR == 0 && p.lda % 4 == 0 && p.R > 0;
-    if (tile == 128 && whole_ok && (p.I % 128 || p.J % 128) && p.I % 64 == 0 && p.J % 64 == 0) tile = 64;
-    if (env_tile == 64 || env_tile == 128) tile = env_tile;
-    dim3 grid((unsigned)((p.J + tile - 1) / tile), (unsigned)((p.I + tile - 1) / tile), 1);
-    const int chunks = (p.R + adapt::STE_TR - 1) / adapt::STE_TR;
-    const long long tiles = (long long)grid.x * grid.y;
-    p.cps = chunks > 0 ? chunks : 1;
-    int parts = 1;
-    if (partials && p.im2col && tile == 64 && tiles < cus && chunks >= 8) {       // (the kernels split only in their unfolded-input form)
-        int want = (int)((2 * cus + tiles - 1) / tiles);
-        if (want > chunks / 4) want = chunks / 4;                   // at least four chunks per part
-        if (want >= 2) {
-            p.cps = (chunks + want - 1) / want;
-            parts = (chunks + p.cps - 1) / p.cps;
-        }
-    }
-    if (parts > 1) { grid.z = (unsigned)parts; p.c = partials; p.o = nullptr; }
-    int ks = tiles * parts < 2 * cus ? 2 : 1;
-    if (env_ks == 1 || env_ks == 2) ks = env_ks;
-    const bool full = aligned && p.I % tile == 0 && p.J % tile == 0 && p.R % adapt::STE_TR == 0 && p.lda % 4 == 0 && p.R > 0;
-#define STE_LAUNCH4(AT, T, F, U) \
-    do { if (ks == 2) adapt::ste_gemm_kernel<AT, T, F, 2, U><<<grid, adapt::STE_THREADS * 2, 0, s>>>(p); \
-         else adapt::ste_gemm_kernel<AT, T, F, 1, U><<<grid, adapt::STE_THREADS, 0, s>>>(p); } while (0)
-#define STE_LAUNCH2(AT, T, U) do { if (full) STE_LAUNCH4(AT, T, true, U); else STE_LAUNCH4(AT, T, false, U); } while (0)
-    if (a_t && p.im2col) { if (tile == 128) STE_LAUNCH2(true, 128, true); else STE_LAUNCH2(true, 64, true); }
-    else if (a_t) { if (tile == 128) STE_LAUNCH2(true, 128, false); else STE_LAUNCH2(true, 64, false); }
-    else { if (tile == 128) STE_LAUNCH2(false, 128, false); else STE_LAUNCH2(false, 64, false); }
-#undef STE_LAUNCH2
-#undef STE_LAUNCH4
-    if (parts > 1) {
-        const size_t n = (size_t)p.I * (size_t)p.J;
-        const size_t blocks = (n + 255) / 256;
-        adapt::ste_reduce_masked_kernel<<<(unsigned)(blocks < 4096 ? blocks : 4096), 256, 0, s>>>(partials, parts, n, p_in.o, p_in.so, p_in.Q,
-                                                                                                  p_in.c);
-    }
-}
-
-inline unsigned ew_grid(size_t work_items) {
-    size_t g = (work_items + adapt::EW_THREADS - 1) / adapt::EW_THREADS;
-    if (g < 1) g = 1;
-    if (g > 256 * 16) g = 256 * 16;   // grid-stride loops: 16 blocks per compute unit is plenty
-    return (unsigned)g;
-}
-
-// Debugging aid: with ADAPT_POISON_ALLOC set in the environment every device allocation of the library is filled with
-// 0xA5 bytes before use, so that code which relies on fresh memory being zero shows up in the tests.
-bool poison_on() {
-    static const bool v = getenv("ADAPT_POISON_ALLOC") != nullptr;
-    return v;
-}
-hipError_t dbg_poison(void *p, size_t bytes, hipStream_t s) {
-    if (!poison_on() || !p || bytes < 4) return hipSuccess;
-    adapt::fill_u32_kernel<<<4096, 256, 0, s>>>(static_cast<uint32_t *>(p), 0xA5A5A5A5u, bytes / 4);
-    return hipGetLastError();
-}
-hipError_t dbg_malloc_async(void **p, size_t bytes, hipStream_t s) {
-    hipError_t e = hipMallocAsync(p, bytes, s);
-    if (e == hipSuccess) e = dbg_poison(*p, bytes, s);
-    return e;
-}
-hipError_t dbg_malloc(void **p, size_t bytes) {
-    hipError_t e = hipMalloc(p, bytes);
-    if (e == hipSuccess && poison_on()) {
-        e = dbg_poison(*p, bytes, nullptr);
-        if (e == hipSuccess) e = hipDeviceSynchronize();
-    }
-    return e;
-}
-
-// Scratch memory of one call.  Plain entry points take it from the stream-ordered allocator and give it back in stream
-// order; a packed-weights handle keeps one grow-only buffer, so that its calls allocate nothing once they have run at
-// their largest size (they can then be recorded into a HIP graph).
-struct Workspace {
-    void *ptr = nullptr;
-    size_t bytes = 0;
-};
-
-int ws_get(Workspace *cache, size_t bytes, hipStream_t s, void **out) {
-    if (!cache) {
-        HIP_TRY(dbg_malloc_async(out, bytes, s));
-        return ADAPT_OK;
-    }
-    if (cache->bytes < bytes) {
-        if (cache->ptr) HIP_TRY(hipFree(cache->ptr));       // waits for the device: no earlier call still uses it
-        cache->ptr = nullptr;
-        cache->bytes = 0;
-        HIP_TRY(dbg_malloc(&cache->ptr, bytes));
-        cache->bytes = bytes;
-    }
-    *out = cache->ptr;
-    return ADAPT_OK;
-}
-
-int ws_put(Workspace *cache, void *p, hipStream_t s, int rc) {
-    if (cache || !p) return rc;
-    hipError_t fe = hipFreeAsync(p, s);
-    if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
-    return rc;
-}
 
 // Optional fp32 ends of a layer call.
 struct LayerIO {
@@ -184,23 +35,6 @@ int finish_inplace(int32_t *buf, size_t n, size_t channels, size_t inner, const 
 }
 
 }  // namespace
-
-struct adapt_lut {
-    int bits;
-    int storage;            // 0: one signed 16-bit image; 1: low (unsigned) + high (signed) images
-    int32_t min_entry, max_entry;
-    int device;
-    int rs;                 // entries per image row = 2^b + 2
-    int img_bytes;          // per image, multiple of 16
-    uint16_t *img_dev[2];   // [0] = only / low half, [1] = high half
-    uint16_t *lut16_dev[2]; // same halves, plain [a & mask][w & mask] order (source of the derived line tables)
-};
-
-struct adapt_lut16 {
-    int bits;               // 2..12
-    int device;
-    int32_t *t_dev;         // [w + H][a + H], 2^b x 2^b int32
-};
 
 struct adapt_weights {
     int kind;               // 0 linear, 1 conv2d, 2 transposed conv2d
@@ -240,305 +74,6 @@ struct adapt_weights {
     // adapt::RowsParams), made on first use
     mutable uint32_t *wofs_cell_dev;
 };
-
-extern "C" {
-
-const char *adapt_last_error(void) { return g_err; }
-
-int adapt_device_cu_count(void) {
-    int dev = 0, cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return fail(ADAPT_ERR_HIP, "hipGetDevice failed");
-    if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-        return fail(ADAPT_ERR_HIP, "hipDeviceGetAttribute failed");
-    return cu;
-}
-
-int adapt_lut_create(adapt_lut **out, int bits, const int32_t *table_host) {
-    if (!out) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lut_create: out is NULL");
-    *out = nullptr;
-    if (!table_host) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lut_create: table_host is NULL");
-    if (bits < 2 || bits > 8) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lut_create: bits=%d not in [2,8]", bits);
-    const int n = 1 << bits;
-    int32_t lo = table_host[0], hi = table_host[0];
-    for (int i = 0; i < n * n; ++i) {
-        if (table_host[i] < lo) lo = table_host[i];
-        if (table_host[i] > hi) hi = table_host[i];
-    }
-    adapt_lut *l = new (std::nothrow) adapt_lut();
-    if (!l) return fail(ADAPT_ERR_OUT_OF_MEMORY, "adapt_lut_create: host allocation failed");
-    l->bits = bits;
-    l->min_entry = lo;
-    l->max_entry = hi;
-    l->storage = (lo >= -32768 && hi <= 32767) ? 0 : 1;
-    l->rs = n + 2;
-    l->img_bytes = ((n * l->rs * 2 + 15) / 16) * 16;
-    l->img_dev[0] = l->img_dev[1] = nullptr;
-    l->lut16_dev[0] = l->lut16_dev[1] = nullptr;
-    if (hipGetDevice(&l->device) != hipSuccess) {
-        delete l;
-        return fail(ADAPT_ERR_HIP, "adapt_lut_create: hipGetDevice failed");
-    }
-    // private image order: row = weight operand, column = activation operand, then a zero column
-    std::vector<uint16_t> img((size_t)l->img_bytes / 2, 0);
-    for (int half = 0; half <= l->storage; ++half) {
-        for (int w = 0; w < n; ++w)
-            for (int a = 0; a < n; ++a) {
-                const uint32_t v = (uint32_t)table_host[(size_t)a * n + w];
-                uint16_t e;
-                if (l->storage == 0) e = (uint16_t)v;
-                else e = half == 0 ? (uint16_t)(v & 0xffffu) : (uint16_t)(v >> 16);
-                img[(size_t)w * l->rs + a] = e;
-            }
-        hipError_t e = dbg_malloc((void **)&l->img_dev[half], (size_t)l->img_bytes);
-        if (e == hipSuccess) e = hipMemcpy(l->img_dev[half], img.data(), (size_t)l->img_bytes, hipMemcpyHostToDevice);
-        // plain copy indexed by the two's-complement wrap of the operands: [a & mask][w & mask]
-        std::vector<uint16_t> plain((size_t)n * n);
-        const int hh = n >> 1;
-        for (int a = -hh; a < hh; ++a)
-            for (int w = -hh; w < hh; ++w)
-                plain[(size_t)(a & (n - 1)) * n + (w & (n - 1))] = img[(size_t)(w + hh) * l->rs + (a + hh)];
-        if (e == hipSuccess) e = dbg_malloc((void **)&l->lut16_dev[half], plain.size() * 2);
-        if (e == hipSuccess) e = hipMemcpy(l->lut16_dev[half], plain.data(), plain.size() * 2, hipMemcpyHostToDevice);
-        if (e != hipSuccess) {
-            for (int j = 0; j < 2; ++j) {
-                if (l->img_dev[j]) (void)hipFree(l->img_dev[j]);
-                if (l->lut16_dev[j]) (void)hipFree(l->lut16_dev[j]);
-            }
-            delete l;
-            return fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP,
-                        "adapt_lut_create: device image: %s", hipGetErrorString(e));
-        }
-    }
-    *out = l;
-    return ADAPT_OK;
-}
-
-int adapt_lut_destroy(adapt_lut *lut) {
-    if (!lut) return ADAPT_OK;
-    for (int j = 0; j < 2; ++j) {
-        if (lut->img_dev[j]) (void)hipFree(lut->img_dev[j]);
-        if (lut->lut16_dev[j]) (void)hipFree(lut->lut16_dev[j]);
-    }
-    delete lut;
-    return ADAPT_OK;
-}
-
-int adapt_lut_info(const adapt_lut *lut, int *bits, int *storage, int32_t *min_entry, int32_t *max_entry) {
-    if (!lut) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lut_info: lut is NULL");
-    if (bits) *bits = lut->bits;
-    if (storage) *storage = lut->storage;
-    if (min_entry) *min_entry = lut->min_entry;
-    if (max_entry) *max_entry = lut->max_entry;
-    return ADAPT_OK;
-}
-
-/* ------------------------------------------------------------------ quantiser / dequantiser */
-
-int adapt_absmax_f32(const float *x_dev, size_t n, float *amax_dev, void *stream) {
-    if (!amax_dev || (!x_dev && n)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_absmax_f32: NULL pointer");
-    hipStream_t s = (hipStream_t)stream;
-    adapt::fill_u32_kernel<<<1, 64, 0, s>>>(reinterpret_cast<uint32_t *>(amax_dev), 0u, 1);
-    if (n) {
-        const int vec = aligned16(x_dev) ? 1 : 0;
-        adapt::absmax_kernel<<<ew_grid(n / 8 + 1), adapt::EW_THREADS, 0, s>>>(x_dev, n, reinterpret_cast<uint32_t *>(amax_dev), vec);
-    }
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-int adapt_quantize_f32(const float *x_dev, int8_t *q_dev, size_t n, float scale, int bits, void *stream) {
-    if ((!x_dev || !q_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_quantize_f32: NULL pointer");
-    if (bits < 2 || bits > 8) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_quantize_f32: bits=%d not in [2,8]", bits);
-    if (!(scale > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_quantize_f32: scale must be > 0");
-    if (n == 0) return ADAPT_OK;
-    const int vec = (aligned16(x_dev) && aligned16(q_dev)) ? 1 : 0;
-    const float Q = (float)((1 << (bits - 1)) - 1);
-    adapt::quantize_kernel<<<ew_grid(n / 16 + 1), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, q_dev, n, scale, Q, vec);
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-int adapt_dequant_i32(const int32_t *acc_dev, float *y_dev, size_t outer, size_t channels, size_t inner,
-                      float scale, const float *bias_dev, void *stream) {
-    const size_t n = outer * channels * inner;
-    if ((!acc_dev || !y_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_dequant_i32: NULL pointer");
-    if (n == 0) return ADAPT_OK;
-    const int vec = (aligned16(acc_dev) && aligned16(y_dev) && (!bias_dev || inner % 4 == 0)) ? 1 : 0;
-    adapt::dequant_kernel<<<ew_grid(n / 4 + 1), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(acc_dev, y_dev, n, channels, inner, scale, bias_dev, vec);
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-int adapt_ste_linear_backward_f32(const float *dy_dev, const float *x_dev, const float *w_dev, int M, int K, int N, float s_x,
-                                  float s_w, int bits, float *dx_dev, float *dw_dev, float *db_dev, void *stream) {
-    const char *who = "adapt_ste_linear_backward_f32";
-    if (M < 0 || K < 0 || N < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: negative size", who);
-    if (bits < 2 || bits > 16) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bits=%d not in [2,16]", who, bits);
-    if (!(s_x > 0.0f) || !(s_w > 0.0f) || s_x > 3.0e38f || s_w > 3.0e38f)
-        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: scales must be finite and > 0", who);
-    const bool want_dx = dx_dev && M > 0 && K > 0, want_dw = dw_dev && N > 0 && K > 0, want_db = db_dev && N > 0;
-    if ((want_dx || want_dw || want_db) && M > 0 && N > 0 && !dy_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL dy_dev", who);
-    if ((want_dx || want_dw) && ((M > 0 && !x_dev) || (N > 0 && !w_dev))) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL x_dev / w_dev", who);
-    for (const void *q : {(const void *)dy_dev, (const void *)x_dev, (const void *)w_dev, (const void *)dx_dev, (const void *)dw_dev, (const void *)db_dev})
-        if (reinterpret_cast<uintptr_t>(q) & 3u) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: pointer not aligned to 4 bytes", who);
-    if ((dx_dev && (dx_dev == x_dev || dx_dev == dy_dev || dx_dev == w_dev)) || (dw_dev && (dw_dev == w_dev || dw_dev == dy_dev || dw_dev == x_dev)))
-        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: a gradient must not alias an input", who);
-    if (((long long)M + 63) / 64 > 65535 || ((long long)N + 63) / 64 > 65535)
-        return fail(ADAPT_ERR_UNSUPPORTED, "%s: M and N are limited to %d", who, 65535 * 64);
-    hipStream_t s = (hipStream_t)stream;
-    const float Q = (float)((1 << (bits - 1)) - 1);
-    if (want_dx) {          // dx [M][K] = inside(x) * dy [M][N] . fq(w) [N][K]
-        adapt::SteParams p{};
-        p.a = dy_dev; p.b = w_dev; p.o = x_dev; p.c = dx_dev;
-        p.I = M; p.J = K; p.R = N; p.lda = N;
-        p.sb = s_w; p.so = s_x; p.Q = Q;
-        launch_ste_gemm(p, false, aligned16(dy_dev) && aligned16(w_dev), s);
-        HIP_TRY(hipGetLastError());
-    }
-    if (want_dw) {          // dw [N][K] = inside(w) * dy^T [N][M] . fq(x) [M][K]
-        adapt::SteParams p{};
-        p.a = dy_dev; p.b = x_dev; p.o = w_dev; p.c = dw_dev;
-        p.I = N; p.J = K; p.R = M; p.lda = N;
-        p.sb = s_x; p.so = s_w; p.Q = Q;
-        launch_ste_gemm(p, true, aligned16(dy_dev) && aligned16(x_dev), s);
-        HIP_TRY(hipGetLastError());
-    }
-    if (want_db) {
-        adapt::ste_colsum_kernel<<<(unsigned)((N + 31) / 32), adapt::STE_COLSUM_THREADS, 0, s>>>(dy_dev, db_dev, M, N);
-        HIP_TRY(hipGetLastError());
-    }
-    return ADAPT_OK;
-}
-
-namespace {
-adapt::FastDiv fast_div(uint32_t d);
-struct SteConvPlan {
-    adapt::SteConvGeo g;
-    long long M, K;
-    size_t rows_bytes, col_bytes, wp_bytes, part_bytes, total;
-};
-int ste_conv_plan(SteConvPlan *pl, int N, int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w, int pad_h, int pad_w,
-                  int dil_h, int dil_w, bool want_dx, bool want_dw, const char *who) {
-    if (N < 0 || Cin < 1 || H < 1 || W < 1 || Cout < 1 || kh < 1 || kw < 1 || stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0 ||
-        dil_h < 1 || dil_w < 1)
-        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
-    const long long Ho = ((long long)H + 2LL * pad_h - (long long)dil_h * (kh - 1) - 1) / stride_h + 1;
-    const long long Wo = ((long long)W + 2LL * pad_w - (long long)dil_w * (kw - 1) - 1) / stride_w + 1;
-    if ((long long)H + 2LL * pad_h < (long long)dil_h * (kh - 1) + 1 || (long long)W + 2LL * pad_w < (long long)dil_w * (kw - 1) + 1)
-        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: the filter does not fit the padded image", who);
-    pl->M = (long long)N * Ho * Wo;
-    pl->K = (long long)Cin * kh * kw;
-    if (pl->M > 65535LL * 64 || pl->K > 0x7fffffffLL || Ho > 0x7fffffffLL || Wo > 0x7fffffffLL || (long long)N * Cin * H * W > (1LL << 40))
-        return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor too large (N Ho Wo is limited to %d)", who, 65535 * 64);
-    if ((long long)H * W > 0x7fffffffLL || Ho * Wo > 0x7fffffffLL)
-        return fail(ADAPT_ERR_UNSUPPORTED, "%s: an image plane is limited to 2^31 - 1 pixels", who);
-    adapt::SteConvGeo &g = pl->g;
-    g = adapt::SteConvGeo{};
-    g.N = N; g.C = Cin; g.H = H; g.W = W; g.O = Cout; g.kh = kh; g.kw = kw; g.sh = stride_h; g.sw = stride_w; g.ph = pad_h; g.pw = pad_w;
-    g.dh = dil_h; g.dw = dil_w; g.Ho = (int)Ho; g.Wo = (int)Wo;
-    g.dK = fast_div((uint32_t)pl->K); g.dkw = fast_div((uint32_t)kw); g.dkhkw = fast_div((uint32_t)(kh * kw)); g.dWo = fast_div((uint32_t)Wo);
-    g.dHoWo = fast_div((uint32_t)(Ho * Wo)); g.dC = fast_div((uint32_t)Cin); g.dW = fast_div((uint32_t)W); g.dHW = fast_div((uint32_t)(H * W));
-    g.dO = fast_div((uint32_t)Cout); g.dP = fast_div((uint32_t)(Ho * Wo)); g.dsh = fast_div((uint32_t)stride_h); g.dsw = fast_div((uint32_t)stride_w);
-    auto up = [](size_t b) { return (b + 255) / 256 * 256; };
-    pl->rows_bytes = up((size_t)pl->M * Cout * sizeof(float));
-    pl->col_bytes = up((size_t)pl->M * (size_t)pl->K * sizeof(float));
-    pl->part_bytes = up(STE_PARTIAL_FLOATS * sizeof(float));
-    pl->wp_bytes = want_dx ? up((size_t)Cout * (size_t)pl->K * sizeof(float)) : 0;
-    pl->total = pl->rows_bytes + (want_dx ? pl->col_bytes : 0) + pl->wp_bytes + pl->part_bytes;
-    return ADAPT_OK;
-}
-}  // namespace
-
-int adapt_ste_conv2d_backward_workspace(int N, int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w, int pad_h,
-                                        int pad_w, int dil_h, int dil_w, int want_dx, int want_dw, size_t *bytes) {
-    const char *who = "adapt_ste_conv2d_backward_workspace";
-    if (!bytes) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
-    SteConvPlan pl;
-    int rc = ste_conv_plan(&pl, N, Cin, H, W, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, want_dx != 0, want_dw != 0, who);
-    if (rc) return rc;
-    *bytes = pl.total;
-    return ADAPT_OK;
-}
-
-int adapt_ste_conv2d_backward_f32(const float *dy_dev, const float *x_dev, const float *w_dev, int N, int Cin, int H, int W, int Cout,
-                                  int kh, int kw, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, float s_x,
-                                  float s_w, int bits, float *dx_dev, float *dw_dev, float *db_dev, void *workspace_dev,
-                                  size_t workspace_bytes, void *stream) {
-    const char *who = "adapt_ste_conv2d_backward_f32";
-    if (bits < 2 || bits > 16) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bits=%d not in [2,16]", who, bits);
-    if (!(s_x > 0.0f) || !(s_w > 0.0f) || s_x > 3.0e38f || s_w > 3.0e38f)
-        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: scales must be finite and > 0", who);
-    SteConvPlan pl;
-    int rc = ste_conv_plan(&pl, N, Cin, H, W, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, dx_dev != nullptr,
-                           dw_dev != nullptr, who);
-    if (rc) return rc;
-    if (pl.M > 0 && (!dy_dev || !x_dev || !w_dev)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
-    for (const void *q : {(const void *)dy_dev, (const void *)x_dev, (const void *)w_dev, (const void *)dx_dev, (const void *)dw_dev,
-                          (const void *)db_dev})
-        if (reinterpret_cast<uintptr_t>(q) & 3u) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: pointer not aligned to 4 bytes", who);
-    if ((dx_dev && (dx_dev == x_dev || dx_dev == dy_dev || dx_dev == w_dev)) || (dw_dev && (dw_dev == w_dev || dw_dev == dy_dev || dw_dev == x_dev)))
-        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: a gradient must not alias an input", who);
-    if (!dx_dev && !dw_dev && !db_dev) return ADAPT_OK;
-    hipStream_t s = (hipStream_t)stream;
-    const adapt::SteConvGeo &g = pl.g;
-    const float Q = (float)((1 << (bits - 1)) - 1);
-    const size_t w_elems = (size_t)Cout * (size_t)pl.K, x_elems = (size_t)N * Cin * H * W;
-    if (pl.M == 0) {        // no samples: the weight and bias gradients are zero, there is no input gradient
-        if (dw_dev) adapt::fill_u32_kernel<<<ew_grid(w_elems), 256, 0, s>>>(reinterpret_cast<uint32_t *>(dw_dev), 0u, w_elems);
-        if (db_dev) adapt::fill_u32_kernel<<<ew_grid((size_t)Cout), 256, 0, s>>>(reinterpret_cast<uint32_t *>(db_dev), 0u, (size_t)Cout);
-        HIP_TRY(hipGetLastError());
-        return ADAPT_OK;
-    }
-    if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 255u) || workspace_bytes < pl.total)
-        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: workspace of %zu bytes, aligned to 256, needed (adapt_ste_conv2d_backward_workspace)", who,
-                    pl.total);
-    char *ws = static_cast<char *>(workspace_dev);
-    float *rows = reinterpret_cast<float *>(ws);
-    float *dcol = dx_dev ? reinterpret_cast<float *>(ws + pl.rows_bytes) : nullptr;
-    float *partials = reinterpret_cast<float *>(ws + pl.total - pl.part_bytes);      // used by one kernel pair at a time (stream order)
-    const int M = (int)pl.M, K = (int)pl.K, P = g.Ho * g.Wo;
-    const size_t rows_n = (size_t)M * Cout, col_n = (size_t)M * K;     // (col_n: elements of dcol)
-    if (rows_n < 0x7fffffffull) adapt::ste_rows_from_nchw_kernel<uint32_t><<<ew_grid(rows_n), 256, 0, s>>>(dy_dev, rows, g, rows_n);
-    else adapt::ste_rows_from_nchw_kernel<size_t><<<ew_grid(rows_n), 256, 0, s>>>(dy_dev, rows, g, rows_n);
-    HIP_TRY(hipGetLastError());
-    if (dw_dev) {           // dw [Cout][K] = inside(w) * rows^T [Cout][M] . fq(col(x)) [M][K], col(x) read from x itself
-        adapt::SteParams p{};
-        p.a = rows; p.b = x_dev; p.o = w_dev; p.c = dw_dev;
-        p.I = Cout; p.J = K; p.R = M; p.lda = Cout;
-        p.sb = s_x; p.so = s_w; p.Q = Q;
-        p.im2col = 1; p.g = g;
-        launch_ste_gemm(p, true, true, s, partials);        // (both operands lie in the workspace)
-        HIP_TRY(hipGetLastError());
-    }
-    if (dx_dev) {           // dcol [M][K] = rows [M][Cout] . fq(w) [Cout][K]; dx = inside(x) * the taps of dcol gathered onto the image
-        adapt::SteParams p{};
-        float *wp = reinterpret_cast<float *>(ws + pl.rows_bytes + pl.col_bytes);      // the weights with the channel last in each row
-        adapt::ste_taps_first_kernel<<<ew_grid(w_elems), 256, 0, s>>>(w_dev, wp, Cout, Cin, kh * kw);
-        HIP_TRY(hipGetLastError());
-        p.a = rows; p.b = wp; p.o = nullptr; p.c = dcol;
-        p.I = M; p.J = K; p.R = Cout; p.lda = Cout;
-        p.sb = s_w; p.so = 1.0f; p.Q = Q;
-        launch_ste_gemm(p, false, true, s);
-        HIP_TRY(hipGetLastError());
-        if (x_elems < 0x7fffffffull && col_n < 0x7fffffffull)
-            adapt::ste_col2im_kernel<uint32_t><<<ew_grid(x_elems), 256, 0, s>>>(dcol, x_dev, dx_dev, g, s_x, Q, x_elems);
-        else adapt::ste_col2im_kernel<size_t><<<ew_grid(x_elems), 256, 0, s>>>(dcol, x_dev, dx_dev, g, s_x, Q, x_elems);
-        HIP_TRY(hipGetLastError());
-    }
-    if (db_dev) {
-        const int Z = N < 16 ? N : 16;
-        if ((size_t)Z * Cout <= STE_PARTIAL_FLOATS && Z > 1) {
-            adapt::ste_bias_grad_nchw_kernel<<<dim3((unsigned)Cout, (unsigned)Z), 256, 0, s>>>(dy_dev, partials, N, Cout, P);
-            adapt::ste_reduce_masked_kernel<<<(unsigned)((Cout + 255) / 256), 256, 0, s>>>(partials, Z, (size_t)Cout, nullptr, 1.0f, Q, db_dev);
-        } else {
-            adapt::ste_bias_grad_nchw_kernel<<<dim3((unsigned)Cout, 1), 256, 0, s>>>(dy_dev, db_dev, N, Cout, P);
-        }
-        HIP_TRY(hipGetLastError());
-    }
-    return ADAPT_OK;
-}
-
-}  // extern "C"
 
 /* ------------------------------------------------------------------ table-lookup matrix products */
 
@@ -667,7 +202,6 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     return rc;
 }
 
-adapt::FastDiv fast_div(uint32_t d);
 
 // Grouped convolution with fewer than 8 output channels per group (depthwise and its relatives): direct form
 // io: whole-layer form (fp32 activations in, rescaled fp32 / chained output): only the tiled kernel has it, so the call is
@@ -932,21 +466,6 @@ struct LinesCall {       // per-call geometry of the activation side
     size_t out_channels = 1, out_inner = 1;     // where the channel sits in a flat output index: (i / inner) % channels
 };
 
-int device_cus() {
-    int cu = 256, dev = 0;
-    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
-    return cu;
-}
-
-adapt::FastDiv fast_div(uint32_t d) {
-    int l = 0;
-    while ((1ull << l) < d) ++l;
-    adapt::FastDiv f;
-    f.k = 31 + l;
-    f.M = (uint32_t)((1ull << f.k) / d + 1);
-    f.d = d;
-    return f;
-}
 
 // How a product is spread over the chip.  Rows per lane R (a workgroup handles 128 R rows): as many as still give every
 // compute unit a workgroup, because table traffic per multiply-accumulate falls with R.  When even the largest tile
@@ -1757,81 +1276,6 @@ int adapt_approx_conv2d_packed(const adapt_weights *h, const int8_t *x_dev, int3
                         pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream, &h->ws, nullptr, h);
 }
 
-/* ------------------------------------------------------------------ per-channel ranges, percentile calibrator */
-
-int adapt_absmax_rows_f32(const float *x_dev, size_t rows, size_t cols, float *amax_dev, void *stream) {
-    if (rows == 0) return ADAPT_OK;
-    if (!amax_dev || (!x_dev && cols)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_absmax_rows_f32: NULL pointer");
-    if (rows > 0x7fffffffULL) return fail(ADAPT_ERR_UNSUPPORTED, "adapt_absmax_rows_f32: more than 2^31-1 rows");
-    adapt::absmax_rows_kernel<<<(unsigned)rows, adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, cols, amax_dev);
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-int adapt_quantize_rows_f32(const float *x_dev, int8_t *q_dev, size_t rows, size_t cols, const float *scales_dev, int bits,
-                            void *stream) {
-    if (bits < 2 || bits > 8) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_quantize_rows_f32: bits=%d not in [2,8]", bits);
-    if (rows == 0 || cols == 0) return ADAPT_OK;
-    if (!x_dev || !q_dev || !scales_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_quantize_rows_f32: NULL pointer");
-    adapt::quantize_rows_kernel<<<ew_grid(rows * cols), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(
-        x_dev, q_dev, rows, cols, scales_dev, (float)((1 << (bits - 1)) - 1));
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-int adapt_dequant_i32_per_channel(const int32_t *acc_dev, float *y_dev, size_t outer, size_t channels, size_t inner,
-                                  const float *scales_dev, const float *bias_dev, void *stream) {
-    const size_t n = outer * channels * inner;
-    if (n == 0) return ADAPT_OK;
-    if (!acc_dev || !y_dev || !scales_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_dequant_i32_per_channel: NULL pointer");
-    adapt::dequant_pc_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(acc_dev, y_dev, n, channels, inner, scales_dev,
-                                                                                        bias_dev);
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-int adapt_histogram_abs_f32(const float *x_dev, size_t n, float amax, int bins, uint32_t *counts_dev, void *stream) {
-    if (bins < 1 || bins > 4096) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_histogram_abs_f32: bins=%d not in [1,4096]", bins);
-    if (!(amax > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_histogram_abs_f32: amax must be > 0");
-    if (!counts_dev || (!x_dev && n)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_histogram_abs_f32: NULL pointer");
-    if (n == 0) return ADAPT_OK;
-    const float width = amax / (float)bins;
-    adapt::histogram_abs_kernel<<<ew_grid(n / 8 + 1), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, n, width, bins, counts_dev);
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-int adapt_percentile_from_histogram(const uint32_t *counts_dev, int bins, float amax, unsigned num, unsigned den, float *calib_max_dev,
-                                    void *stream) {
-    if (bins < 1 || bins > 4096) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_percentile_from_histogram: bins=%d not in [1,4096]", bins);
-    if (!(amax > 0.0f) || den == 0 || num > den || den > (1u << 20))
-        return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_percentile_from_histogram: need amax > 0 and 0 <= num <= den <= 2^20");
-    if (!counts_dev || !calib_max_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_percentile_from_histogram: NULL pointer");
-    adapt::percentile_kernel<<<1, 64, 0, (hipStream_t)stream>>>(counts_dev, bins, amax / (float)bins, num, den, calib_max_dev);
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-int adapt_mse_from_histogram(const uint32_t *counts_dev, int bins, float amax, int bits, float *calib_max_dev, void *stream) {
-    if (bins < 1 || bins > 4096) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_mse_from_histogram: bins=%d not in [1,4096]", bins);
-    if (!(amax > 0.0f) || bits < 2 || bits > 16) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_mse_from_histogram: need amax > 0 and 2 <= bits <= 16");
-    if (!counts_dev || !calib_max_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_mse_from_histogram: NULL pointer");
-    hipStream_t s = (hipStream_t)stream;
-    double *err = nullptr;
-    HIP_TRY(dbg_malloc_async((void **)&err, (size_t)bins * sizeof(double), s));
-    const float width = amax / (float)bins;
-    adapt::mse_candidates_kernel<<<(unsigned)((bins + 255) / 256), 256, 0, s>>>(counts_dev, bins, width, (float)((1 << (bits - 1)) - 1), err);
-    hipError_t e = hipGetLastError();
-    if (e == hipSuccess) {
-        adapt::mse_pick_kernel<<<1, 64, 0, s>>>(err, bins, width, calib_max_dev);
-        e = hipGetLastError();
-    }
-    hipError_t fe = hipFreeAsync(err, s);
-    if (e != hipSuccess) return fail(ADAPT_ERR_HIP, "adapt_mse_from_histogram: %s", hipGetErrorString(e));
-    if (fe != hipSuccess) return fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
-    return ADAPT_OK;
-}
-
 /* ------------------------------------------------------------------ whole layers, fp32 in and out */
 
 static int layer_io(LayerIO *io, const adapt_weights *h, const float *x_dev, const float *y_dev, float s_x, float s_out,
@@ -2238,342 +1682,6 @@ int adapt_rnn_step_f32(const adapt_weights *h, const int8_t *qh_dev, const int32
     ls.Hs = Hs; ls.acc_ih = acc_ih_dev; ls.bias = bias_dev; ls.c = nullptr; ls.h = h_dev; ls.qh_next = qh_next_dev;
     ls.s_ih = s_ih; ls.s_hh = s_hh; ls.s_h = s_h; ls.Qh = (float)((1 << (h->bits - 1)) - 1);
     return run_rows(h->lut, qh_dev, nullptr, nullptr, g, s, h->wofs_cell_dev, Hs, nullptr, &ls);
-}
-
-/* ------------------------------------------------------------------ fp32 operations between layers */
-
-int adapt_relu_f32(const float *x_dev, float *y_dev, size_t n, void *stream) {
-    if ((!x_dev || !y_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_relu_f32: NULL pointer");
-    if (!n) return ADAPT_OK;
-    adapt::relu_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, y_dev, n);
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-int adapt_add_f32(const float *a_dev, const float *b_dev, float *y_dev, size_t n, int relu, void *stream) {
-    if ((!a_dev || !b_dev || !y_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_add_f32: NULL pointer");
-    if (!n) return ADAPT_OK;
-    adapt::add_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(a_dev, b_dev, y_dev, n, relu);
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-int adapt_relu_backward_f32(const float *dy_dev, const float *y_dev, float *dx_dev, size_t n, void *stream) {
-    if ((!dy_dev || !y_dev || !dx_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_relu_backward_f32: NULL pointer");
-    if (!n) return ADAPT_OK;
-    adapt::relu_backward_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(dy_dev, y_dev, dx_dev, n);
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-int adapt_sgd_step_f32(float *w_dev, const float *g_dev, size_t n, float lr, void *stream) {
-    if ((!w_dev || !g_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_sgd_step_f32: NULL pointer");
-    if (w_dev == g_dev && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_sgd_step_f32: w_dev and g_dev must differ");
-    if (!n) return ADAPT_OK;
-    adapt::sgd_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(w_dev, g_dev, n, lr);
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-int adapt_avgpool_hw_f32(const float *x_dev, float *y_dev, size_t NC, size_t HW, void *stream) {
-    if ((!x_dev || !y_dev) && NC) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_avgpool_hw_f32: NULL pointer");
-    if (HW == 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_avgpool_hw_f32: HW is 0");
-    if (!NC) return ADAPT_OK;
-    if (HW == 64 && (reinterpret_cast<uintptr_t>(x_dev) & 15u) == 0 && (NC + 63) / 64 <= 0x7fffffffull)
-        adapt::avgpool64_kernel<<<(unsigned)((NC + 63) / 64), 64, 0, (hipStream_t)stream>>>(x_dev, y_dev, NC);
-    else
-        adapt::avgpool_kernel<<<(unsigned)((NC + adapt::EW_THREADS - 1) / adapt::EW_THREADS), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, y_dev, NC, HW);
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-int adapt_shortcut_a_f32(const float *x_dev, float *y_dev, int N, int Cin, int H, int W, int Cout, void *stream) {
-    if (N < 0 || Cin < 1 || H < 1 || W < 1 || Cout < Cin) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_shortcut_a_f32: bad dimension");
-    if (N == 0) return ADAPT_OK;
-    if (!x_dev || !y_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_shortcut_a_f32: NULL pointer");
-    if (x_dev == y_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_shortcut_a_f32: in-place not possible");
-    const size_t total = (size_t)N * Cout * ((H + 1) / 2) * ((W + 1) / 2);
-    const int fast = total < 0x7fffffffull && (size_t)N * Cin * H * W < 0x7fffffffull ? 1 : 0;
-    adapt::shortcut_a_kernel<<<ew_grid(total), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(
-        x_dev, y_dev, N, Cin, H, W, Cout, fast_div((uint32_t)((W + 1) / 2)), fast_div((uint32_t)((H + 1) / 2)), fast_div((uint32_t)Cout), fast);
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-static int unary(const float *x_dev, float *y_dev, size_t n, int op, void *stream, const char *who) {
-    if ((!x_dev || !y_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
-    if (!n) return ADAPT_OK;
-    adapt::unary_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, y_dev, n, op);
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-int adapt_tanh_f32(const float *x_dev, float *y_dev, size_t n, void *stream) { return unary(x_dev, y_dev, n, 0, stream, "adapt_tanh_f32"); }
-int adapt_sigmoid_f32(const float *x_dev, float *y_dev, size_t n, void *stream) { return unary(x_dev, y_dev, n, 1, stream, "adapt_sigmoid_f32"); }
-
-static int lstm_cell(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh, const float *bias_dev, float *c_dev,
-                     float *h_dev, int8_t *qh_dev, float s_h, int bits, int B, int Hs, void *stream, const char *who) {
-    if (B < 0 || Hs < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: negative dimension", who);
-    const size_t n = (size_t)B * Hs;
-    if (!n) return ADAPT_OK;
-    if (!acc_ih_dev || !acc_hh_dev || !c_dev || !h_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
-    adapt::lstm_cell_kernel<<<(unsigned)((n + adapt::EW_THREADS - 1) / adapt::EW_THREADS), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(
-        acc_ih_dev, acc_hh_dev, s_ih, s_hh, bias_dev, c_dev, h_dev, B, Hs, qh_dev, s_h, (float)((1 << (bits - 1)) - 1));
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-int adapt_lstm_cell_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh,
-                        const float *bias_dev, float *c_dev, float *h_dev, int B, int Hs, void *stream) {
-    return lstm_cell(acc_ih_dev, acc_hh_dev, s_ih, s_hh, bias_dev, c_dev, h_dev, nullptr, 1.0f, 8, B, Hs, stream, "adapt_lstm_cell_f32");
-}
-
-int adapt_lstm_cell_q_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh, const float *bias_dev,
-                          float *c_dev, float *h_dev, int8_t *qh_dev, float s_h, int bits, int B, int Hs, void *stream) {
-    if (!qh_dev && (size_t)B * Hs) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lstm_cell_q_f32: NULL pointer");
-    if (bits < 2 || bits > 8) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lstm_cell_q_f32: bits=%d not in [2,8]", bits);
-    if (!(s_h > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lstm_cell_q_f32: scale must be > 0");
-    return lstm_cell(acc_ih_dev, acc_hh_dev, s_ih, s_hh, bias_dev, c_dev, h_dev, qh_dev, s_h, bits, B, Hs, stream, "adapt_lstm_cell_q_f32");
-}
-
-static int cell_args(const char *who, const void *a, const void *b, const void *h, const int8_t *qh, float s_h, int bits, int B, int Hs,
-                     size_t *n) {
-    if (B < 0 || Hs < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: negative dimension", who);
-    *n = (size_t)B * Hs;
-    if (!*n) return ADAPT_OK;
-    if (!a || !b || !h) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
-    if (qh) {
-        if (bits < 2 || bits > 8) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bits=%d not in [2,8]", who, bits);
-        if (!(s_h > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: scale must be > 0", who);
-    }
-    return ADAPT_OK;
-}
-
-int adapt_gru_cell_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh, const float *b_ih_dev,
-                       const float *b_hh_dev, const float *h_prev_dev, float *h_dev, int8_t *qh_dev, float s_h, int bits, int B,
-                       int Hs, void *stream) {
-    size_t n = 0;
-    int rc = cell_args("adapt_gru_cell_f32", acc_ih_dev, acc_hh_dev, h_dev, qh_dev, s_h, bits, B, Hs, &n);
-    if (rc || !n) return rc;
-    if (!h_prev_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_gru_cell_f32: NULL pointer");
-    adapt::gru_cell_kernel<<<(unsigned)((n + adapt::EW_THREADS - 1) / adapt::EW_THREADS), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(
-        acc_ih_dev, acc_hh_dev, s_ih, s_hh, b_ih_dev, b_hh_dev, h_prev_dev, h_dev, B, Hs, qh_dev, s_h,
-        qh_dev ? (float)((1 << (bits - 1)) - 1) : 1.0f);
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-int adapt_rnn_cell_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, float s_ih, float s_hh, const float *bias_dev, int relu,
-                       float *h_dev, int8_t *qh_dev, float s_h, int bits, int B, int Hs, void *stream) {
-    size_t n = 0;
-    int rc = cell_args("adapt_rnn_cell_f32", acc_ih_dev, acc_hh_dev, h_dev, qh_dev, s_h, bits, B, Hs, &n);
-    if (rc || !n) return rc;
-    adapt::rnn_cell_kernel<<<(unsigned)((n + adapt::EW_THREADS - 1) / adapt::EW_THREADS), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(
-        acc_ih_dev, acc_hh_dev, s_ih, s_hh, bias_dev, relu, h_dev, B, Hs, qh_dev, s_h, qh_dev ? (float)((1 << (bits - 1)) - 1) : 1.0f);
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-
-/* ------------------------------------------------------------------ operands wider than 8 bits, function multipliers */
-
-int adapt_lut16_create(adapt_lut16 **out, int bits, const int32_t *table_host) {
-    if (!out) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lut16_create: out is NULL");
-    *out = nullptr;
-    if (!table_host) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lut16_create: table_host is NULL");
-    if (bits < 2 || bits > 12) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lut16_create: bits=%d not in [2,12]", bits);
-    const size_t bytes = ((size_t)1 << (2 * bits)) * sizeof(int32_t);
-    adapt_lut16 *l = new (std::nothrow) adapt_lut16();
-    if (!l) return fail(ADAPT_ERR_OUT_OF_MEMORY, "adapt_lut16_create: host allocation failed");
-    l->bits = bits; l->t_dev = nullptr; l->device = 0;
-    int32_t *tmp = nullptr;
-    (void)hipGetDevice(&l->device);
-    hipError_t e = dbg_malloc((void **)&l->t_dev, bytes);
-    if (e == hipSuccess) e = dbg_malloc((void **)&tmp, bytes);
-    if (e == hipSuccess) e = hipMemcpy(tmp, table_host, bytes, hipMemcpyHostToDevice);
-    if (e == hipSuccess) {
-        adapt::big_transpose_kernel<<<ew_grid(bytes / 4), 256, 0, nullptr>>>(tmp, l->t_dev, bits);
-        e = hipGetLastError();
-    }
-    if (e == hipSuccess) e = hipDeviceSynchronize();
-    if (tmp) (void)hipFree(tmp);
-    if (e != hipSuccess) {
-        if (l->t_dev) (void)hipFree(l->t_dev);
-        delete l;
-        (void)hipGetLastError();
-        return fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "adapt_lut16_create: %s", hipGetErrorString(e));
-    }
-    *out = l;
-    return ADAPT_OK;
-}
-
-static int func_args(const char *who, int kind, int param, int bits, int max_bits) {
-    if (kind < 0 || kind > 2) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: kind=%d not in [0,2]", who, kind);
-    if (bits < 2 || bits > max_bits) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bits=%d not in [2,%d]", who, bits, max_bits);
-    if (param < 0 || param >= bits) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: param=%d not in [0,bits)", who, param);
-    return ADAPT_OK;
-}
-
-int adapt_lut16_create_from_func(adapt_lut16 **out, int kind, int param, int bits) {
-    if (!out) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lut16_create_from_func: out is NULL");
-    *out = nullptr;
-    int rc = func_args("adapt_lut16_create_from_func", kind, param, bits, 12);
-    if (rc) return rc;
-    const size_t entries = (size_t)1 << (2 * bits);
-    adapt_lut16 *l = new (std::nothrow) adapt_lut16();
-    if (!l) return fail(ADAPT_ERR_OUT_OF_MEMORY, "adapt_lut16_create_from_func: host allocation failed");
-    l->bits = bits; l->t_dev = nullptr; l->device = 0;
-    (void)hipGetDevice(&l->device);
-    hipError_t e = dbg_malloc((void **)&l->t_dev, entries * sizeof(int32_t));
-    if (e == hipSuccess) {
-        adapt::big_table_from_func_kernel<<<ew_grid(entries), 256, 0, nullptr>>>(l->t_dev, bits, kind, param);
-        e = hipGetLastError();
-    }
-    if (e == hipSuccess) e = hipDeviceSynchronize();
-    if (e != hipSuccess) {
-        if (l->t_dev) (void)hipFree(l->t_dev);
-        delete l;
-        (void)hipGetLastError();
-        return fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "adapt_lut16_create_from_func: %s",
-                    hipGetErrorString(e));
-    }
-    *out = l;
-    return ADAPT_OK;
-}
-
-int adapt_lut16_destroy(adapt_lut16 *lut) {
-    if (!lut) return ADAPT_OK;
-    if (lut->t_dev) (void)hipFree(lut->t_dev);
-    delete lut;
-    return ADAPT_OK;
-}
-
-int adapt_lut16_bits(const adapt_lut16 *lut) {
-    if (!lut) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_lut16_bits: lut is NULL");
-    return lut->bits;
-}
-
-int adapt_quantize_i16_f32(const float *x_dev, int16_t *q_dev, size_t n, float scale, int bits, void *stream) {
-    if ((!x_dev || !q_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_quantize_i16_f32: NULL pointer");
-    if (bits < 2 || bits > 16) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_quantize_i16_f32: bits=%d not in [2,16]", bits);
-    if (!(scale > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_quantize_i16_f32: scale must be > 0");
-    if (n == 0) return ADAPT_OK;
-    adapt::quantize_i16_kernel<<<ew_grid(n), 256, 0, (hipStream_t)stream>>>(x_dev, q_dev, n, scale, (float)((1 << (bits - 1)) - 1));
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
-}
-
-}  // extern "C"
-
-namespace {
-
-// table form: lut != nullptr; function form: lut == nullptr and (kind, param)
-int run_big(const adapt_lut16 *lut, int kind, int param, const int16_t *x, const int16_t *w, int32_t *out, adapt::BigParams p, hipStream_t s) {
-    if (p.M == 0 || p.N == 0) return ADAPT_OK;
-    const long long K = (long long)p.taps * p.Cin;
-    const int NT = lut ? adapt::BIG_NT_TABLE : adapt::BIG_NT_FUNC, threads = lut ? adapt::BIG_THREADS_TABLE : adapt::BIG_THREADS_FUNC;
-    p.Npad = (p.N + NT - 1) / NT * NT;
-    if (K * p.Npad > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "weights with more than 2^31-1 packed words");
-    const long long wgs = (long long)((p.M + threads - 1) / threads) * (p.Npad / NT);
-    if (wgs > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "too many workgroups");
-    int32_t *words = nullptr;
-    HIP_TRY(dbg_malloc_async((void **)&words, (size_t)(K > 0 ? K : 1) * p.Npad * sizeof(int32_t), s));
-    int rc = ADAPT_OK;
-    if (K > 0) {
-        const size_t n = (size_t)K * p.Npad;
-        adapt::big_pack_weights_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(w, words, (int)K, p.N, p.Npad, p.Cin, p.taps,
-                                                                                 lut ? lut->bits : 0);
-        hipError_t pe = hipGetLastError();
-        if (pe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "big_pack_weights launch: %s", hipGetErrorString(pe));
-    }
-    p.x = x; p.words = words; p.out = out;
-    const dim3 grid((unsigned)wgs);
-    if (rc == ADAPT_OK) {
-        constexpr int FN = adapt::BIG_NT_FUNC, FT = adapt::BIG_THREADS_FUNC;
-        if (lut) {
-            adapt::MulTable mt{lut->t_dev, 1 << (lut->bits - 1), (1 << lut->bits) - 1};
-            adapt::big_rows_kernel<adapt::MulTable, adapt::BIG_NT_TABLE, adapt::BIG_THREADS_TABLE, true><<<grid, threads, 0, s>>>(p, mt);
-        } else if (kind == adapt::FUNC_EXACT) {
-            adapt::big_rows_kernel<adapt::MulFunc<adapt::FUNC_EXACT>, FN, FT, false><<<grid, threads, 0, s>>>(p, adapt::MulFunc<adapt::FUNC_EXACT>{param});
-        } else if (kind == adapt::FUNC_TRUNC) {
-            adapt::big_rows_kernel<adapt::MulFunc<adapt::FUNC_TRUNC>, FN, FT, false><<<grid, threads, 0, s>>>(p, adapt::MulFunc<adapt::FUNC_TRUNC>{param});
-        } else {
-            adapt::big_rows_kernel<adapt::MulFunc<adapt::FUNC_MITCHELL>, FN, FT, false><<<grid, threads, 0, s>>>(p, adapt::MulFunc<adapt::FUNC_MITCHELL>{param});
-        }
-        hipError_t le = hipGetLastError();
-        if (le != hipSuccess) rc = fail(ADAPT_ERR_HIP, "big_rows launch: %s", hipGetErrorString(le));
-    }
-    hipError_t fe = hipFreeAsync(words, s);
-    if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
-    return rc;
-}
-
-int big_linear(const char *who, const adapt_lut16 *lut, int kind, int param, const int16_t *a, const int16_t *w, int32_t *acc, int M,
-               int K, int N, void *stream) {
-    if (M < 0 || K < 0 || N < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: negative dimension", who);
-    if (M == 0 || N == 0) return ADAPT_OK;
-    if (!acc || (K > 0 && (!a || !w))) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
-    if ((long long)M * N > 0x7fffffffLL || (long long)M * K > 0x7fffffffLL || (long long)N * K > 0x7fffffffLL)
-        return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
-    adapt::BigParams p{};
-    p.M = M; p.N = N; p.conv = 0; p.Cin = K; p.taps = 1; p.kw = 1;
-    p.H = p.W = p.Wo = p.HoWo = 1; p.sh = p.sw = p.dh = p.dw = 1; p.ph = p.pw = 0;
-    p.kstride = 1; p.img_stride = K;
-    return run_big(lut, kind, param, a, w, acc, p, (hipStream_t)stream);
-}
-
-int big_conv2d(const char *who, const adapt_lut16 *lut, int kind, int param, const int16_t *x, const int16_t *w, int32_t *acc, int N,
-               int Cin, int H, int W, int Cout, int kh, int kw, int sh, int sw, int ph, int pw, int dh, int dw, void *stream) {
-    if (N < 0 || Cin < 1 || H < 1 || W < 1 || Cout < 1 || kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0 || dh < 1 || dw < 1)
-        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
-    const long long eh = (long long)H + 2LL * ph - (long long)dh * (kh - 1) - 1, ew = (long long)W + 2LL * pw - (long long)dw * (kw - 1) - 1;
-    if (eh < 0 || ew < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: filter larger than padded input", who);
-    const long long Ho = eh / sh + 1, Wo = ew / sw + 1;
-    if (N == 0) return ADAPT_OK;
-    if (!x || !w || !acc) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
-    if ((long long)N * Cout * Ho * Wo > 0x7fffffffLL || (long long)N * Cin * H * W > 0x7fffffffLL ||
-        (long long)Cout * Cin * kh * kw > 0x7fffffffLL)
-        return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
-    adapt::BigParams p{};
-    p.M = (int)(N * Ho * Wo); p.N = Cout; p.conv = 1; p.Cin = Cin; p.taps = kh * kw; p.kw = kw;
-    p.H = H; p.W = W; p.Wo = (int)Wo; p.HoWo = (int)(Ho * Wo);
-    p.sh = sh; p.sw = sw; p.ph = ph; p.pw = pw; p.dh = dh; p.dw = dw;
-    p.kstride = H * W; p.img_stride = Cin * H * W;
-    return run_big(lut, kind, param, x, w, acc, p, (hipStream_t)stream);
-}
-
-}  // namespace
-
-extern "C" {
-
-int adapt_approx_linear_i16(const adapt_lut16 *lut, const int16_t *a_dev, const int16_t *w_dev, int32_t *acc_dev, int M, int K, int N,
-                            void *stream) {
-    if (!lut) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_linear_i16: lut is NULL");
-    return big_linear("adapt_approx_linear_i16", lut, 0, 0, a_dev, w_dev, acc_dev, M, K, N, stream);
-}
-
-int adapt_approx_linear_func_i16(int kind, int param, int bits, const int16_t *a_dev, const int16_t *w_dev, int32_t *acc_dev, int M,
-                                 int K, int N, void *stream) {
-    int rc = func_args("adapt_approx_linear_func_i16", kind, param, bits, 16);
-    if (rc) return rc;
-    return big_linear("adapt_approx_linear_func_i16", nullptr, kind, param, a_dev, w_dev, acc_dev, M, K, N, stream);
-}
-
-int adapt_approx_conv2d_i16(const adapt_lut16 *lut, const int16_t *x_dev, const int16_t *w_dev, int32_t *acc_dev, int N, int Cin, int H,
-                            int W, int Cout, int kh, int kw, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
-                            void *stream) {
-    if (!lut) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_approx_conv2d_i16: lut is NULL");
-    return big_conv2d("adapt_approx_conv2d_i16", lut, 0, 0, x_dev, w_dev, acc_dev, N, Cin, H, W, Cout, kh, kw, stride_h, stride_w, pad_h,
-                      pad_w, dil_h, dil_w, stream);
-}
-
-int adapt_approx_conv2d_func_i16(int kind, int param, int bits, const int16_t *x_dev, const int16_t *w_dev, int32_t *acc_dev, int N,
-                                 int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w, int pad_h, int pad_w,
-                                 int dil_h, int dil_w, void *stream) {
-    int rc = func_args("adapt_approx_conv2d_func_i16", kind, param, bits, 16);
-    if (rc) return rc;
-    return big_conv2d("adapt_approx_conv2d_func_i16", nullptr, kind, param, x_dev, w_dev, acc_dev, N, Cin, H, W, Cout, kh, kw, stride_h,
-                      stride_w, pad_h, pad_w, dil_h, dil_w, stream);
 }
 
 }  // extern "C"

@@ -21,14 +21,14 @@ struct FastDiv {
     __device__ __forceinline__ uint32_t div(uint32_t n) const { return (uint32_t)(((uint64_t)n * M) >> k); }
 };
 
-__global__ void fill_u32_kernel(uint32_t *p, uint32_t v, size_t n) {       // any grid: strides over n
+static __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, size_t n) {       // any grid: strides over n
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
 }
 
 // max |x|: the bit pattern of a non-negative float orders like an unsigned integer, so the final
 // combine is an integer atomic max; NaNs fail the comparison and are skipped.
-__global__ __launch_bounds__(EW_THREADS) void absmax_kernel(const float *__restrict__ x, size_t n,
+static __global__ __launch_bounds__(EW_THREADS) void absmax_kernel(const float *__restrict__ x, size_t n,
                                                             uint32_t *__restrict__ out_bits, int vec) {
     float m = 0.0f;
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
@@ -60,7 +60,7 @@ __device__ __forceinline__ int quant1(float x, float scale, float Q) {
     return (int)r;
 }
 
-__global__ __launch_bounds__(EW_THREADS) void quantize_kernel(const float *__restrict__ x, int8_t *__restrict__ q,
+static __global__ __launch_bounds__(EW_THREADS) void quantize_kernel(const float *__restrict__ x, int8_t *__restrict__ q,
                                                               size_t n, float scale, float Q, int vec) {
     // 16 values per thread step: four 16-byte loads, one 16-byte store (vec: both pointers 16-byte aligned)
     const size_t n16 = vec ? n / 16 : 0;
@@ -88,7 +88,7 @@ __global__ __launch_bounds__(EW_THREADS) void quantize_kernel(const float *__res
 // channel, activation range from a histogram percentile
 
 // amax[r] = max |x[r][0..cols)|; one workgroup per row
-__global__ __launch_bounds__(EW_THREADS) void absmax_rows_kernel(const float *__restrict__ x, size_t cols, float *__restrict__ amax) {
+static __global__ __launch_bounds__(EW_THREADS) void absmax_rows_kernel(const float *__restrict__ x, size_t cols, float *__restrict__ amax) {
     __shared__ float part[EW_THREADS / 64];
     const float *row = x + (size_t)blockIdx.x * cols;
     float m = 0.0f;
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(EW_THREADS) void absmax_rows_kernel(const float *__
 }
 
 // q[r][c] = quantise(x[r][c], scale[r])
-__global__ __launch_bounds__(EW_THREADS) void quantize_rows_kernel(const float *__restrict__ x, int8_t *__restrict__ q, size_t rows,
+static __global__ __launch_bounds__(EW_THREADS) void quantize_rows_kernel(const float *__restrict__ x, int8_t *__restrict__ q, size_t rows,
                                                                    size_t cols, const float *__restrict__ scale, float Q) {
     const size_t n = rows * cols;
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(EW_THREADS) void quantize_rows_kernel(const float *
 }
 
 // y = float(acc) * scale[c] (+ bias[c])
-__global__ __launch_bounds__(EW_THREADS) void dequant_pc_kernel(const int32_t *__restrict__ acc, float *__restrict__ y, size_t n,
+static __global__ __launch_bounds__(EW_THREADS) void dequant_pc_kernel(const int32_t *__restrict__ acc, float *__restrict__ y, size_t n,
                                                                 size_t channels, size_t inner, const float *__restrict__ scale,
                                                                 const float *__restrict__ bias) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(EW_THREADS) void dequant_pc_kernel(const int32_t *_
 // counts[bin(|x_i|)] += 1 with bins equal bins over [0, amax]: bin(a) = min(bins - 1, trunc(a / width)), width = amax / bins
 // (both IEEE fp32 divisions); NaN is not counted.  Per-workgroup histogram in LDS (bins <= 4096), then one atomic per
 // non-empty bin.
-__global__ __launch_bounds__(EW_THREADS) void histogram_abs_kernel(const float *__restrict__ x, size_t n, float width, int bins,
+static __global__ __launch_bounds__(EW_THREADS) void histogram_abs_kernel(const float *__restrict__ x, size_t n, float width, int bins,
                                                                    uint32_t *__restrict__ counts) {
     __shared__ uint32_t h[4096];
     for (int b = threadIdx.x; b < bins; b += EW_THREADS) h[b] = 0;
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(EW_THREADS) void histogram_abs_kernel(const float *
 }
 
 // calib_max = (k + 1) * width for the first bin k at which the cumulative count reaches ceil(total * num / den)
-__global__ void percentile_kernel(const uint32_t *__restrict__ counts, int bins, float width, unsigned long long num,
+static __global__ void percentile_kernel(const uint32_t *__restrict__ counts, int bins, float width, unsigned long long num,
                                   unsigned long long den, float *__restrict__ out) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
     unsigned long long total = 0;
@@ -172,7 +172,7 @@ __global__ void percentile_kernel(const uint32_t *__restrict__ counts, int bins,
 // value at the centre c_j = (j + 0.5) * width of bin j is reproduced as min(Q, rint(c_j / s)) * s; err[k] = sum_j
 // counts[j] * (c_j - that)^2 in fp64, j ascending, every operation rounded on its own (the library is compiled without
 // contraction).  One thread per candidate.
-__global__ __launch_bounds__(256) void mse_candidates_kernel(const uint32_t *__restrict__ counts, int bins, float width, float Qf,
+static __global__ __launch_bounds__(256) void mse_candidates_kernel(const uint32_t *__restrict__ counts, int bins, float width, float Qf,
                                                              double *__restrict__ err) {
     __shared__ uint32_t cnt[4096];
     for (int j = threadIdx.x; j < bins; j += 256) cnt[j] = counts[j];
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(256) void mse_candidates_kernel(const uint32_t *__r
 }
 
 // the first candidate with the smallest error: calib_max = (k + 1) * width
-__global__ void mse_pick_kernel(const double *__restrict__ err, int bins, float width, float *__restrict__ out) {
+static __global__ void mse_pick_kernel(const double *__restrict__ err, int bins, float width, float *__restrict__ out) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
     int best_k = 0;
     double best = err[0];
@@ -205,7 +205,7 @@ __global__ void mse_pick_kernel(const double *__restrict__ err, int bins, float 
 }
 
 // y = float(acc) * scale (+ bias[c]); channel of flat index i is (i / inner) % channels
-__global__ __launch_bounds__(EW_THREADS) void dequant_kernel(const int32_t *__restrict__ acc, float *__restrict__ y,
+static __global__ __launch_bounds__(EW_THREADS) void dequant_kernel(const int32_t *__restrict__ acc, float *__restrict__ y,
                                                              size_t n, size_t channels, size_t inner, float scale,
                                                              const float *__restrict__ bias, int vec) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
@@ -238,7 +238,7 @@ __global__ __launch_bounds__(EW_THREADS) void dequant_kernel(const int32_t *__re
     }
 }
 
-__global__ __launch_bounds__(EW_THREADS) void relu_kernel(const float *x, float *y, size_t n) {
+static __global__ __launch_bounds__(EW_THREADS) void relu_kernel(const float *x, float *y, size_t n) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
     for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
         const float v = x[i];
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(EW_THREADS) void relu_kernel(const float *x, float 
     }
 }
 
-__global__ __launch_bounds__(EW_THREADS) void add_kernel(const float *a, const float *b, float *y, size_t n, int relu) {
+static __global__ __launch_bounds__(EW_THREADS) void add_kernel(const float *a, const float *b, float *y, size_t n, int relu) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
     for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
         float v = a[i] + b[i];
@@ -256,19 +256,19 @@ __global__ __launch_bounds__(EW_THREADS) void add_kernel(const float *a, const f
 }
 
 // gradient through the fused ReLU: dx = dy where the layer's output y is positive
-__global__ __launch_bounds__(EW_THREADS) void relu_backward_kernel(const float *__restrict__ dy, const float *__restrict__ y, float *__restrict__ dx, size_t n) {
+static __global__ __launch_bounds__(EW_THREADS) void relu_backward_kernel(const float *__restrict__ dy, const float *__restrict__ y, float *__restrict__ dx, size_t n) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
     for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) dx[i] = y[i] > 0.0f ? dy[i] : 0.0f;
 }
 
 // plain stochastic-gradient step of the retraining loop: w <- w - lr * g, the product and the difference rounded separately
-__global__ __launch_bounds__(EW_THREADS) void sgd_kernel(float *__restrict__ w, const float *__restrict__ g, size_t n, float lr) {
+static __global__ __launch_bounds__(EW_THREADS) void sgd_kernel(float *__restrict__ w, const float *__restrict__ g, size_t n, float lr) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
     for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) w[i] = w[i] - lr * g[i];
 }
 
 // one thread per (n, c) plane: the sum order (row-major, sequential) is part of the definition
-__global__ __launch_bounds__(EW_THREADS) void avgpool_kernel(const float *__restrict__ x, float *__restrict__ y,
+static __global__ __launch_bounds__(EW_THREADS) void avgpool_kernel(const float *__restrict__ x, float *__restrict__ y,
                                                              size_t NC, size_t HW) {
     const size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
     if (i >= NC) return;
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(EW_THREADS) void avgpool_kernel(const float *__rest
 // The same for planes of 64 elements (an 8 x 8 feature map), 64 planes per workgroup of 64 lanes: the planes are read
 // with coalesced 16-byte loads into LDS (row pitch 65 words, so that lane t summing plane t meets no bank conflict),
 // then every lane adds up its plane in the same sequential order as above.
-__global__ __launch_bounds__(64) void avgpool64_kernel(const float *__restrict__ x, float *__restrict__ y, size_t NC) {
+static __global__ __launch_bounds__(64) void avgpool64_kernel(const float *__restrict__ x, float *__restrict__ y, size_t NC) {
     __shared__ float tile[64 * 65];
     const size_t p0 = (size_t)blockIdx.x * 64;
     const int t = threadIdx.x;
@@ -301,7 +301,7 @@ __global__ __launch_bounds__(64) void avgpool64_kernel(const float *__restrict__
     y[p0 + t] = s * inv;
 }
 
-__global__ __launch_bounds__(EW_THREADS) void shortcut_a_kernel(const float *__restrict__ x, float *__restrict__ y,
+static __global__ __launch_bounds__(EW_THREADS) void shortcut_a_kernel(const float *__restrict__ x, float *__restrict__ y,
                                                                 int N, int Cin, int H, int W, int Cout, FastDiv dwo, FastDiv dho,
                                                                 FastDiv dco, int fast) {
     const int Ho = (H + 1) / 2, Wo = (W + 1) / 2, padc = (Cout - Cin) / 2;
@@ -362,7 +362,7 @@ __device__ __forceinline__ float tanh_spec(float x) {
     return x < 0.0f ? -t : t;
 }
 
-__global__ __launch_bounds__(EW_THREADS) void unary_kernel(const float *x, float *y, size_t n, int op) {
+static __global__ __launch_bounds__(EW_THREADS) void unary_kernel(const float *x, float *y, size_t n, int op) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
     for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
         const float v = x[i];
@@ -370,7 +370,7 @@ __global__ __launch_bounds__(EW_THREADS) void unary_kernel(const float *x, float
     }
 }
 
-__global__ __launch_bounds__(EW_THREADS) void lstm_cell_kernel(const int32_t *__restrict__ acc_ih,
+static __global__ __launch_bounds__(EW_THREADS) void lstm_cell_kernel(const int32_t *__restrict__ acc_ih,
                                                                const int32_t *__restrict__ acc_hh, float s_ih,
                                                                float s_hh, const float *__restrict__ bias,
                                                                float *__restrict__ c, float *__restrict__ h, int B,
@@ -405,7 +405,7 @@ __global__ __launch_bounds__(EW_THREADS) void lstm_cell_kernel(const int32_t *__
 // rounded fp32 operation in this order:
 //   gi = float(acc_ih) * s_ih (+ b_ih);  gh = float(acc_hh) * s_hh (+ b_hh)
 //   r = sigmoid(gi_r + gh_r);  z = sigmoid(gi_z + gh_z);  n = tanh(gi_n + r * gh_n);  h' = (1 - z) * n + z * h
-__global__ __launch_bounds__(EW_THREADS) void gru_cell_kernel(const int32_t *__restrict__ acc_ih, const int32_t *__restrict__ acc_hh,
+static __global__ __launch_bounds__(EW_THREADS) void gru_cell_kernel(const int32_t *__restrict__ acc_ih, const int32_t *__restrict__ acc_hh,
                                                               float s_ih, float s_hh, const float *__restrict__ b_ih,
                                                               const float *__restrict__ b_hh, const float *h_prev, float *h, int B,
                                                               int Hs, int8_t *__restrict__ qh, float s_h, float Qh) {
@@ -436,7 +436,7 @@ __global__ __launch_bounds__(EW_THREADS) void gru_cell_kernel(const int32_t *__r
 }
 
 // Plain recurrent cell: h' = act((float(acc_ih) * s_ih + float(acc_hh) * s_hh) + bias), act = tanh or ReLU
-__global__ __launch_bounds__(EW_THREADS) void rnn_cell_kernel(const int32_t *__restrict__ acc_ih, const int32_t *__restrict__ acc_hh,
+static __global__ __launch_bounds__(EW_THREADS) void rnn_cell_kernel(const int32_t *__restrict__ acc_ih, const int32_t *__restrict__ acc_hh,
                                                               float s_ih, float s_hh, const float *__restrict__ bias, int relu,
                                                               float *__restrict__ h, int B, int Hs, int8_t *__restrict__ qh, float s_h,
                                                               float Qh) {

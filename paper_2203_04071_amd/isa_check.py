@@ -9,7 +9,7 @@ and the wait that covers it, no instruction may touch the destination registers.
 model the in-order retirement of lgkmcnt / vmcnt; loads issued behind a scalar branch inside an asm statement count as
 issued only while the loop goes on (they are dropped at a backward branch).
 
-  python -m paper_2203_04071_amd.isa_check            compiles csrc/api.hip to assembly and checks it
+  python -m paper_2203_04071_amd.isa_check            compiles the translation units that hold hand-scheduled kernels to assembly and checks them
   python -m paper_2203_04071_amd.isa_check file.s     checks an existing assembly file
 """
 import os
@@ -109,11 +109,11 @@ def check(path, pattern):
     print(f"checked {nfn} functions, {bad} violations")
     return bad
 
-def compile_to_asm(out_path):
-    from .build import HIPCC_FLAGS, SOURCES
+def compile_to_asm(source, out_path):
+    from .build import HIPCC_FLAGS
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
-    cmd = [hipcc] + flags + ["-S", "--cuda-device-only", "-o", out_path] + SOURCES
+    cmd = [hipcc] + flags + ["-S", "--cuda-device-only", "-o", out_path, source]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc -S failed:\n" + r.stdout + r.stderr)
@@ -121,10 +121,14 @@ def compile_to_asm(out_path):
 
 def check_build(pattern='lut_lines_(fast_|wide_)?kernel|lut_grouped_tiled_kernel'):
     """Number of violations in a fresh compilation of the library's device code."""
+    from .build import HAND_SCHEDULED
+    bad = 0
     with tempfile.TemporaryDirectory() as d:
-        path = os.path.join(d, "api.s")
-        compile_to_asm(path)
-        return check(path, pattern)
+        for i, source in enumerate(HAND_SCHEDULED):
+            path = os.path.join(d, "tu%d.s" % i)
+            compile_to_asm(source, path)
+            bad += check(path, pattern)
+    return bad
 
 
 if __name__ == '__main__':
