@@ -391,7 +391,7 @@ int adapt_approx_conv2d_func_i16(int kind, int param, int bits, const int16_t *x
  * [N][K], db_dev [N]: device pointers, fully overwritten; any of them may be NULL (not computed); none may alias an
  * input.  Products and sums are fp32 (matrix instructions for dx / dw, a fixed order for db); NaN inputs get no
  * gradient.  Asynchronous on `stream`, no allocation.  Errors: ADAPT_ERR_INVALID_ARGUMENT (NULL / misaligned pointer,
- * negative size, bits, scales), ADAPT_ERR_UNSUPPORTED (M or N above 65535 * 128), ADAPT_ERR_HIP. */
+ * negative size, bits, scales), ADAPT_ERR_UNSUPPORTED (M or N above 65535 * 64), ADAPT_ERR_HIP. */
 int adapt_ste_linear_backward_f32(const float *dy_dev, const float *x_dev, const float *w_dev, int M, int K, int N, float s_x,
                                   float s_w, int bits, float *dx_dev, float *dw_dev, float *db_dev, void *stream);
 
@@ -420,7 +420,7 @@ int adapt_ste_conv2d_backward_f32(const float *dy_dev, const float *x_dev, const
  * Asynchronous on `stream`.  Errors: ADAPT_ERR_INVALID_ARGUMENT (NULL pointer), ADAPT_ERR_HIP. */
 int adapt_relu_backward_f32(const float *dy_dev, const float *y_dev, float *dx_dev, size_t n, void *stream);
 
-/* One plain stochastic-gradient step, the optimiser the paper retrains with (Sec. IV-A, "Quantization and retraining":
+/* One plain stochastic-gradient step, the optimiser the paper retrains with (Sec. V-A, "Quantization and retraining":
  * SGD, learning rate 1e-4): w[i] <- w[i] - lr * g[i] in fp32, the product and the difference rounded separately.
  * w_dev, g_dev: n floats each on the device, distinct; in place on w_dev.  Asynchronous on `stream`.
  * Errors: ADAPT_ERR_INVALID_ARGUMENT (NULL pointer, w_dev == g_dev), ADAPT_ERR_HIP. */

@@ -77,7 +77,7 @@ def ste_linear_backward_bound(dy, x, w, s_x, s_w, bits):
 
 
 def sgd_step(w, g, lr) -> np.ndarray:
-    """One plain SGD step in fp32 (Sec. IV-A: the paper retrains with SGD): w - lr * g, the product rounded, then the difference."""
+    """One plain SGD step in fp32 (Sec. V-A, "Quantization and retraining": the paper retrains with SGD): w - lr * g, the product rounded, then the difference."""
     w = np.asarray(w, dtype=np.float32)
     g = np.asarray(g, dtype=np.float32)
     prod = (np.float32(lr) * g).astype(np.float32)

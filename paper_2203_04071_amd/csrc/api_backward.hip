@@ -23,7 +23,7 @@ constexpr size_t STE_PARTIAL_FLOATS = (size_t)(512 + 256) * 64 * 64;
 void launch_ste_gemm(const adapt::SteParams &p_in, bool a_t, bool aligned, hipStream_t s, float *partials = nullptr) {
     static const int env_tile = ste_env("ADAPT_STE_TILE"), env_ks = ste_env("ADAPT_STE_KS");
     adapt::SteParams p = p_in;
-    const int cus = 256;
+    const int cus = device_cus();
     const long long t128 = (((long long)p.I + 127) / 128) * (((long long)p.J + 127) / 128);
     int tile = 4 * t128 >= 3 * cus ? 128 : 64;
     // whole 64-tiles where 128-tiles would be ragged: the unguarded 16-byte loads are worth more than the larger tile

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -97,9 +98,15 @@ inline int ws_put(Workspace *cache, void *p, hipStream_t s, int rc) {
     return rc;
 }
 
+// compute units of the current device (asked once per device; 256 when there is no device to ask)
 inline int device_cus() {
-    int cu = 256, dev = 0;
-    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    int cu = cached[dev].load(std::memory_order_relaxed);
+    if (cu > 0) return cu;
+    if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0) return 256;
+    cached[dev].store(cu, std::memory_order_relaxed);
     return cu;
 }
 

@@ -3,7 +3,8 @@
 // nothing here falls back to host computation.
 #include "api_common.hpp"
 #include "lut_lines.hpp"
-#include "lut_wide.hpp"
+#include "lut_quad.hpp"
+#include "lines_plan.hpp"
 #include "lut_rows.hpp"
 #include "lut_grouped.hpp"
 
@@ -64,15 +65,15 @@ struct adapt_weights {
     int wofs_npad;
     uint32_t *wofs1_dev;
     int wofs1_npad;
-    // The same derived tables in the wide order (lut_wide.hpp), made on first use by a call whose geometry takes the
-    // wide-line kernel (single-pass tables, 32 | padded channels); from the handle's copy of the weights.
-    mutable uint4 *dtw_dev;
-    // their entries are stored as int8 digits of (entry - dtw_c) when the table's range allows (adapt::wide_entry): the
-    // matrix-pipe instantiations of the wide kernel then do the widening additions
-    mutable int dtw_digits, dtw_c;
-    // linear [4 Hs][Hs] handles used for LSTM time steps: row offsets with the columns in cell order (see
-    // adapt::RowsParams), made on first use
-    mutable uint32_t *wofs_cell_dev;
+    // The same derived tables in the quad order (lut_quad.hpp: 256-byte lines, entries as int8 digits of entry - dtq_c),
+    // made at pack time for single-pass tables with 16 | padded channels; nullptr otherwise.
+    uint4 *dtq_dev;
+    int dtq_c;
+    size_t dtq_bytes;       // transposed convolution: all phases together
+    // linear [G Hs][Hs] handles (G = 4, 3 or 1 gates, even Hs, single-pass table) that can serve recurrent time steps:
+    // row offsets with the columns in cell order (see adapt::RowsParams), made at pack time
+    uint32_t *wofs_cell_dev;
+    int cell_G;
 };
 
 /* ------------------------------------------------------------------ table-lookup matrix products */
@@ -81,11 +82,12 @@ namespace {
 
 template <int NT, bool SIGNED>
 int launch_rows_inst(const adapt::RowsParams &p, dim3 grid, size_t lds, hipStream_t s) {
-    static size_t configured = 0;   // largest dynamic LDS size announced for this instantiation
+    static std::atomic<size_t> configured{0};   // largest dynamic LDS size announced for this instantiation
     auto kern = adapt::lut_rows_kernel<NT, SIGNED>;
-    if (lds > configured) {
+    if (lds > configured.load(std::memory_order_acquire)) {     // (two threads may both announce it: harmless)
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        configured = lds;
+        size_t seen = configured.load(std::memory_order_relaxed);
+        while (seen < lds && !configured.compare_exchange_weak(seen, lds, std::memory_order_release)) {}
     }
     kern<<<grid, adapt::ROWS_THREADS, lds, s>>>(p);
     HIP_TRY(hipGetLastError());
@@ -132,11 +134,7 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
         return ADAPT_OK;
     }
     // tile shape: prefer 16 outputs per lane; shrink the tile until the grid covers the chip
-    int cu = 256;
-    {
-        int dev = 0;
-        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
-    }
+    const int cu = device_cus();
     int NT = 16, MT = 1024;
     auto wgs = [&](int nt, int mt) { return (long long)((g.M + mt - 1) / mt) * ((g.N + nt - 1) / nt) * ngroups; };
     while (MT > 64 && (MT / 2 >= g.M || (wgs(NT, MT) < cu && Ktot / (adapt::ROWS_THREADS / (MT / 2)) >= 16))) MT /= 2;
@@ -221,11 +219,7 @@ int run_grouped(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t 
     p.hoff = 1 << (lut->bits - 1); p.mask = (1 << lut->bits) - 1; p.row_bytes = lut->rs * 2;
     p.total = (size_t)N * Cout * Ho * Wo;
     if (!p.total) return ADAPT_OK;
-    int cu = 256;
-    {
-        int dev = 0;
-        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
-    }
+    const int cu = device_cus();
     // tiled form: the input region of a tile and the tap words of its groups sit in LDS next to the table
     const int taps = kh * kw;
     long long Wr = (long long)(Wo - 1) * sw + (long long)(kw - 1) * dw + 1;
@@ -310,16 +304,17 @@ int run_grouped(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t 
         {adapt::lut_grouped_tiled_kernel<false, 3, 2>, adapt::lut_grouped_tiled_kernel<true, 3, 2>},
         {adapt::lut_grouped_tiled_kernel<false, 5, 2>, adapt::lut_grouped_tiled_kernel<true, 5, 2>},
     };
-    static size_t configured[6][2] = {};
+    static std::atomic<size_t> configured[6][2];
     for (int half = 0; half <= lut->storage; ++half) {
         p.img = lut->img_dev[half];
         p.shift = half == 0 ? -1 : 16;
         const bool sgn = (lut->storage == 0) || half == 1;
         const kern_t kern = tiled ? tiled_kernels[variant][sgn] : (sgn ? adapt::lut_grouped_kernel<true> : adapt::lut_grouped_kernel<false>);
         const int slot = tiled ? variant : 5;
-        if (lds > configured[slot][sgn]) {
+        if (lds > configured[slot][sgn].load(std::memory_order_acquire)) {
             HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            configured[slot][sgn] = lds;
+            size_t seen = configured[slot][sgn].load(std::memory_order_relaxed);
+            while (seen < lds && !configured[slot][sgn].compare_exchange_weak(seen, lds, std::memory_order_release)) {}
         }
         kern<<<(unsigned)blocks, adapt::ROWS_THREADS, lds, s>>>(p);
         HIP_TRY(hipGetLastError());
@@ -370,28 +365,41 @@ int launch_lines_xmajor(const adapt::LinesParams &p, unsigned grid, hipStream_t 
     return ADAPT_OK;
 }
 
-// wide-line kernel: 8 rows per lane from an x-major copy, signed single-pass tables
-// (extra: the instantiation whose epilogue also takes the border terms of a transposed convolution off and knows tanh)
-template <bool EXTRA>
-int launch_lines_wide_mf(const adapt::LinesParams &p, unsigned grid, hipStream_t s) {
-    if (p.bits == 8) adapt::lut_lines_wide_kernel<4, EXTRA, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
-    else if (p.bits == 7) adapt::lut_lines_wide_kernel<2, EXTRA, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
-    else adapt::lut_lines_wide_kernel<1, EXTRA, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+// quad kernel (x-major copy, single-pass tables as int8 digits); extra: the instantiation whose epilogue also takes the
+// border terms of a transposed convolution off, knows tanh and writes the next layer's input copy
+template <int DOPS, int R>
+int launch_quad_inst(const adapt::LinesParams &p, unsigned grid, bool extra, hipStream_t s) {
+    // The kernel's table buffers must start at LDS address 0 (its address arithmetic puts the buffer number into bits
+    // 16 and up): true as long as they are the kernel's only LDS object, which its LDS size tells.
+    static std::atomic<int> checked{0};
+    if (!checked.load(std::memory_order_acquire)) {
+        for (int e = 0; e < 2; ++e) {
+            hipFuncAttributes fa;
+            const void *fn = e ? reinterpret_cast<const void *>(adapt::lut_quad_kernel<DOPS, R, true>)
+                               : reinterpret_cast<const void *>(adapt::lut_quad_kernel<DOPS, R, false>);
+            HIP_TRY(hipFuncGetAttributes(&fa, fn));
+            if (fa.sharedSizeBytes != (size_t)2 * adapt::QUAD_BUF_BYTES)
+                return fail(ADAPT_ERR_HIP, "quad kernel: %zu bytes of LDS instead of the two table buffers alone", (size_t)fa.sharedSizeBytes);
+        }
+        checked.store(1, std::memory_order_release);
+    }
+    if (extra) adapt::lut_quad_kernel<DOPS, R, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    else adapt::lut_quad_kernel<DOPS, R, false><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
     HIP_TRY(hipGetLastError());
     return ADAPT_OK;
 }
 
-int launch_lines_wide(const adapt::LinesParams &p, unsigned grid, bool extra, bool digits, hipStream_t s) {
-    if (digits) return extra ? launch_lines_wide_mf<true>(p, grid, s) : launch_lines_wide_mf<false>(p, grid, s);
-    if (extra) {
-        if (p.bits == 8) adapt::lut_lines_wide_kernel<4, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
-        else if (p.bits == 7) adapt::lut_lines_wide_kernel<2, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
-        else adapt::lut_lines_wide_kernel<1, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
-    } else if (p.bits == 8) adapt::lut_lines_wide_kernel<4><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
-    else if (p.bits == 7) adapt::lut_lines_wide_kernel<2><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
-    else adapt::lut_lines_wide_kernel<1><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
-    HIP_TRY(hipGetLastError());
-    return ADAPT_OK;
+template <int R>
+int launch_quad_r(const adapt::LinesParams &p, unsigned grid, bool extra, hipStream_t s) {
+    if (p.bits == 8) return launch_quad_inst<4, R>(p, grid, extra, s);
+    if (p.bits == 7) return launch_quad_inst<2, R>(p, grid, extra, s);
+    return launch_quad_inst<1, R>(p, grid, extra, s);
+}
+
+int launch_quad(const adapt::LinesParams &p, unsigned grid, int R, bool extra, hipStream_t s) {
+    if (R == 8) return launch_quad_r<8>(p, grid, extra, s);
+    if (R == 4) return launch_quad_r<4>(p, grid, extra, s);
+    return launch_quad_r<2>(p, grid, extra, s);
 }
 
 template <int R>
@@ -453,10 +461,10 @@ struct LinesCall {       // per-call geometry of the activation side
     int xmajor, ch_stride;  // x-major activation copy (see pad_channels_last_kernel) and its bytes per channel step
     int out_plane, out_sy, out_sx;      // see adapt::LinesParams
     std::vector<LinesPhase> phases;
-    // Derived tables in the wide order (lut_wide.hpp) for the x-major case, or nullptr.  Callers only provide it for
-    // single-pass tables without tap pairing.
-    const uint4 *dt_wide = nullptr;
-    int wide_digits = 0, wide_c = 0;    // digit form of those tables and its offset (adapt::wide_entry)
+    LinesPlan plan;                     // from plan_product(): kernel, rows per lane, split of the inner dimension
+    // Derived tables in the quad order (lut_quad.hpp) and the offset of their digit form; needed when the plan says LK_QUAD
+    const uint4 *dt_quad = nullptr;
+    int quad_c = 0;
     int32_t *partial = nullptr;         // room for the partial sums when the plan splits the inner dimension
     // transposed convolution: zero sums and geometry for taking the border terms off inside the kernel (see
     // adapt::LinesParams::zsum); run_lines reports through border_done whether it did
@@ -466,82 +474,67 @@ struct LinesCall {       // per-call geometry of the activation side
     size_t out_channels = 1, out_inner = 1;     // where the channel sits in a flat output index: (i / inner) % channels
 };
 
-
-// How a product is spread over the chip.  Rows per lane R (a workgroup handles 128 R rows): as many as still give every
-// compute unit a workgroup, because table traffic per multiply-accumulate falls with R.  When even the largest tile
-// leaves compute units idle and the inner dimension is long enough, keep R = 8 and split the inner dimension over
-// `ksplit` workgroups instead (each streams only its slice of the tables; a small kernel adds the partial sums).
-struct LinesPlan {
-    int R, ksplit, gps;      // gps: groups of four steps per slice
-};
-
-LinesPlan lines_plan(int M, int tiles, int Cc, int taps) {
-    const int cu = device_cus();
-    auto wgs = [&](int r) { return (long long)((M + 128 * r - 1) / (128 * r)) * tiles; };
-    LinesPlan pl{8, 1, 0};
-    const int groups = Cc % 4 == 0 ? taps * Cc / 4 : 0;        // the split needs the fast kernel
-    if (wgs(8) * 4 <= cu && groups >= 8) {      // (with half the chip covered, 4 rows per lane does as well)
-        int ks = (int)(cu / wgs(8));
-        if (ks > groups / 4) ks = groups / 4;                   // at least four groups (16 steps) per slice
-        if (ks > 16) ks = 16;
-        if (ks >= 2) {
-            pl.gps = (groups + ks - 1) / ks;
-            pl.ksplit = (groups + pl.gps - 1) / pl.gps;
-            return pl;
-        }
-    }
-    while (pl.R > 2 && wgs(pl.R) < cu) pl.R /= 2;
-    pl.gps = groups > 0 ? groups : 1;
-    return pl;
+// The plan of one product (see lines_plan.hpp).  M: rows (per phase); phases: 1, or stride^2 of a transposed convolution;
+// Wo: output width (linear layers: M); sw: horizontal stride; quad_tables: the caller holds tables in the quad order.
+LinesPlan plan_product(const LinesShape &q, int bits, int storage, int M, int phases, int Wo, int sw, bool quad_tables) {
+    PlanIn in;
+    in.M = M; in.tiles = q.n_tiles * phases; in.k_cc = q.k_cc(); in.k_taps = q.k_taps(); in.Wo = Wo; in.sw = sw;
+    in.quad_steps = (quad_tables && storage == 0 && q.Cp % adapt::QUAD_STEP == 0) ? q.kh * q.kw * (q.Cp / adapt::QUAD_STEP) : 0;
+    in.cu = device_cus();
+    (void)bits;
+    return plan_lines(in);
 }
 
-int lines_rows_per_lane(int M, int tiles, int Cc, int taps) { return lines_plan(M, tiles, Cc, taps).R; }
-
 // bytes of partial sums a call needs (0 without a split of the inner dimension)
-size_t lines_partial_bytes(int M, int tiles, int Cc, int taps, size_t out_elems) {
-    const LinesPlan pl = lines_plan(M, tiles, Cc, taps);
+size_t plan_partial_bytes(const LinesPlan &pl, size_t out_elems) {
     return pl.ksplit > 1 ? (size_t)pl.ksplit * out_elems * sizeof(int32_t) : 0;
+}
+
+// bytes of one phase's tables in the quad order
+size_t quad_table_bytes(const LinesShape &q, int bits) {
+    return (size_t)q.n_tiles * q.kh * q.kw * (q.Cp / adapt::QUAD_STEP) * ((size_t)adapt::QUAD_LINE_BYTES << bits);
 }
 
 int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *xt, const LinesCall &c,
               int32_t *out, hipStream_t s, const LayerIO *io = nullptr, bool may_fuse = true, bool *border_done = nullptr,
               bool *finished = nullptr) {
     const int n_phases = (int)c.phases.size();
-    const LinesPlan pl = lines_plan(c.M, q.n_tiles * n_phases, q.k_cc(), q.k_taps());
+    const LinesPlan &pl = c.plan;
     const int R = pl.R;
+    const bool quad = pl.kernel == LK_QUAD;
     const bool split = pl.ksplit > 1;
     if (split && !c.partial) return fail(ADAPT_ERR_HIP, "lines path: no room for partial sums");
+    if (quad && (!c.dt_quad || storage != 0 || !c.xmajor)) return fail(ADAPT_ERR_HIP, "lines path: quad plan without quad tables");
     adapt::LinesParams p;
     p.xt = xt;
     p.M = c.M; p.N = q.N; p.n_tiles = q.n_tiles;
-    p.Cc = q.k_cc(); p.taps = q.k_taps(); p.kw = q.kw; p.bits = bits;
-    p.pair_g = q.pair_g; p.pair_cg = q.Cp / 4; p.taps_real = q.kh * q.kw;
+    p.Cc = quad ? q.Cp / adapt::QUAD_STEP : q.k_cc(); p.taps = quad ? q.kh * q.kw : q.k_taps(); p.kw = q.kw; p.bits = bits;
+    p.pair_g = quad ? 0 : q.pair_g; p.pair_cg = q.Cp / 4; p.taps_real = q.kh * q.kw;
     if (q.pair_g && storage != 0) return fail(ADAPT_ERR_HIP, "lines path: tap pairing with a two-pass table");
     p.HoWo = c.HoWo; p.Wo = c.Wo; p.img_stride = c.img_stride;
     p.oy_stride = c.oy_stride; p.ox_stride = c.ox_stride; p.ky_stride = c.ky_stride; p.kx_stride = c.kx_stride;
     p.ch_stride = c.ch_stride;
     p.out_plane = c.out_plane; p.out_sy = c.out_sy; p.out_sx = c.out_sx;
-    p.m_tiles = (c.M + 128 * R - 1) / (128 * R);
+    p.m_tiles = (c.M + pl.rows_per_wg() - 1) / pl.rows_per_wg();
     p.d_HoWo = fast_div((uint32_t)p.HoWo); p.d_Wo = fast_div((uint32_t)p.Wo);
     p.d_ntiles = fast_div((uint32_t)p.n_tiles); p.d_mtiles = fast_div((uint32_t)p.m_tiles); p.d_phases = fast_div(1u);
     p.ksplit = pl.ksplit; p.gps = pl.gps; p.ks_out_stride = split ? (long long)c.out_elems : 0;
     // digit tables: every real lookup of an output lacks the offset (sums wrap in 32 bits like everything else)
-    p.corr = c.wide_digits ? (int)(uint32_t)((unsigned long long)((long long)q.kh * q.kw * q.Cin * (long long)c.wide_c)) : 0;
+    p.corr = quad ? (int)(uint32_t)((unsigned long long)((long long)q.kh * q.kw * q.Cin * (long long)c.quad_c)) : 0;
     // one base offset per lane is enough when the R rows of a lane are equally spaced in xt
     const bool regular = (c.M % R == 0) && (c.HoWo == 1 || c.Wo % R == 0);
-    const bool xmajor = c.xmajor && R == 8 && c.M % 8 == 0 && c.Wo % 4 == 0;
-    if (c.xmajor && !xmajor) return fail(ADAPT_ERR_HIP, "lines path: x-major copy without 8 rows per lane in runs of 4 pixels");
-    const bool use_wide = xmajor && c.dt_wide && storage == 0 && !q.pair_g;
-    // the wide kernel has an instantiation that takes the border terms of a transposed convolution off itself and
+    const bool xmajor = pl.kernel == LK_XMAJOR;
+    if (c.xmajor != pl.xmajor) return fail(ADAPT_ERR_HIP, "lines path: the activation copy does not have the layout of the plan");
+    // the quad kernel has an instantiation that takes the border terms of a transposed convolution off itself and
     // knows tanh; the kernel that adds split sums knows tanh too
-    const bool border_in_kernel = c.zsum && !split && use_wide;
+    const bool border_in_kernel = c.zsum && !split && quad;
     if (border_done) *border_done = border_in_kernel;
-    const bool act_ok = io && (io->act <= 1 || (io->act == 2 && (split || use_wide)));
+    const bool act_ok = io && (io->act <= 1 || (io->act == 2 && (split || quad)));
     const bool fuse = (may_fuse || border_in_kernel) && io && io->deq && storage == 0 && act_ok;
     if (finished) *finished = fuse;
     const bool fuse_in_kernel = fuse && !split;
     const bool chain_in_kernel = fuse_in_kernel && io->chain.buf;
-    const bool extra = use_wide && (border_in_kernel || (fuse_in_kernel && io->act == 2) || chain_in_kernel);
+    const bool extra = quad && (border_in_kernel || (fuse_in_kernel && io->act == 2) || chain_in_kernel);
     p.chain = chain_in_kernel ? io->chain : adapt::ChainOut{};
     p.zsum = border_in_kernel ? c.zsum : nullptr;
     p.cv_s = fast_div((uint32_t)c.cv_s);
@@ -551,25 +544,25 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     p.scale = fuse_in_kernel ? io->s_out : 1.0f; p.bias = fuse_in_kernel ? io->bias : nullptr;
     p.scales = fuse_in_kernel ? io->s_out_vec : nullptr;
     p.resid = fuse_in_kernel ? io->resid : nullptr;
+    const long long quad_phase_u4 = quad ? (long long)(quad_table_bytes(q, bits) / 16) : 0;
     int rc = ADAPT_OK;
     for (int half = 0; half <= storage && rc == ADAPT_OK; ++half) {
-        p.dt = dt[half];
+        p.dt = quad ? c.dt_quad : dt[half];
         p.out = split ? c.partial : out;
         p.shift = (half == 0 || split) ? -1 : 16;
         const bool sgn = storage == 0 || half == 1;
         for (int first = 0; first < n_phases && rc == ADAPT_OK; first += 4) {       // up to four phases per launch
             p.phases = n_phases - first < 4 ? n_phases - first : 4;
             for (int i = 0; i < 4; ++i) {
-                const LinesPhase &f = c.phases[first + (i < p.phases ? i : 0)];
-                p.xt_off[i] = f.xt_off; p.out_off[i] = f.out_off; p.dt_off[i] = f.dt_off;
+                const int fi = first + (i < p.phases ? i : 0);
+                const LinesPhase &f = c.phases[fi];
+                p.xt_off[i] = f.xt_off; p.out_off[i] = f.out_off; p.dt_off[i] = quad ? (long long)fi * quad_phase_u4 : f.dt_off;
             }
             const long long grid = (long long)p.m_tiles * q.n_tiles * p.phases * p.ksplit;
             if (grid > 0x7fffffffLL) return fail(ADAPT_ERR_UNSUPPORTED, "lines path: grid too large");
             p.d_phases = fast_div((uint32_t)p.phases);
-            if (use_wide) {
-                p.dt = c.dt_wide;
-                rc = launch_lines_wide(p, (unsigned)grid, extra, c.wide_digits != 0, s);
-            } else if (xmajor) rc = sgn ? launch_lines_xmajor<true>(p, (unsigned)grid, s) : launch_lines_xmajor<false>(p, (unsigned)grid, s);
+            if (quad) rc = launch_quad(p, (unsigned)grid, R, extra, s);
+            else if (xmajor) rc = sgn ? launch_lines_xmajor<true>(p, (unsigned)grid, s) : launch_lines_xmajor<false>(p, (unsigned)grid, s);
             else if (R == 8) rc = launch_lines_r<8>(p, (unsigned)grid, sgn, regular, s);
             else if (R == 4) rc = launch_lines_r<4>(p, (unsigned)grid, sgn, regular, s);
             else rc = launch_lines_r<2>(p, (unsigned)grid, sgn, regular, s);
@@ -595,38 +588,31 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     return rc;
 }
 
-// Derived tables of a packed handle in the wide order, made on first use; nullptr when the handle's shape has none
-// (two-pass table, paired taps, channels per tap not a multiple of 32) or memory is short (the caller then stays on
-// the lines kernels).
-const uint4 *ensure_wide(const adapt_weights *h, hipStream_t s) {
-    if (!h) return nullptr;
-    if (h->dtw_dev) return h->dtw_dev;
-    if (h->storage != 0 || h->pair_g || !h->w8_dev || !h->lut || h->Cc % 4 != 0 || h->dt_bytes == 0) return nullptr;
-    uint4 *d = nullptr;
-    if (dbg_malloc((void **)&d, h->dt_bytes) != hipSuccess) {
-        (void)hipGetLastError();
-        return nullptr;
-    }
-    const size_t total = h->dt_bytes / 16;
+// Derived tables of a handle in the quad order (single-pass tables, 16 | padded channels), made when the handle is
+// packed.  Entries are the int8 digits of entry - c with c = smallest entry + 32640 (see adapt::quad_entry).
+int pack_quad(adapt_weights *h, hipStream_t s, const char *who) {
+    if (h->storage != 0 || h->Cp % adapt::QUAD_STEP != 0 || h->Cp == 0) return ADAPT_OK;
+    LinesShape q;
+    q.kind = h->kind; q.N = h->N; q.Cin = h->Cin; q.Cp = h->Cp; q.n_tiles = h->n_tiles;
+    const int phases = h->kind == 2 ? h->stride * h->stride : 1;
+    q.kh = h->kind == 2 ? h->kh / h->stride : h->kh; q.kw = h->kind == 2 ? h->kw / h->stride : h->kw;
+    const size_t bytes = quad_table_bytes(q, h->bits) * phases;
+    if (bytes == 0) return ADAPT_OK;
+    hipError_t e = dbg_malloc((void **)&h->dtq_dev, bytes);
+    if (e != hipSuccess) return fail(e == hipErrorOutOfMemory ? ADAPT_ERR_OUT_OF_MEMORY : ADAPT_ERR_HIP, "%s: hipMalloc(%zu): %s", who, bytes, hipGetErrorString(e));
+    h->dtq_bytes = bytes;
+    h->dtq_c = h->lut->min_entry + 32640;
+    const size_t total = bytes / 16;
     size_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
-    // digit form when every entry minus an offset fits two int8 digits to base -128
-    const long long span = (long long)h->lut->max_entry - (long long)h->lut->min_entry;
-    const int digits = (span <= 32895 && !getenv("ADAPT_WIDE_PLAIN")) ? 1 : 0;
-    const int digit_c = digits ? h->lut->min_entry + 16384 : 0;
     if (h->kind == 2)
-        adapt::pack_wide_tables_convt_kernel<<<(unsigned)blocks, 256, 0, s>>>(h->lut->lut16_dev[0], h->w8_dev, d, h->bits, h->N, h->Cin, h->kh,
-                                                                             h->kw, h->stride, h->Cp, h->n_tiles, digits, digit_c);
+        adapt::pack_quad_tables_convt_kernel<<<(unsigned)blocks, 256, 0, s>>>(h->lut->lut16_dev[0], h->w8_dev, h->dtq_dev, h->bits, h->N, h->Cin,
+                                                                             h->kh, h->kw, h->stride, h->Cp, h->n_tiles, 1, h->dtq_c);
     else
-        adapt::pack_wide_tables_kernel<<<(unsigned)blocks, 256, 0, s>>>(h->lut->lut16_dev[0], h->w8_dev, d, h->bits, h->N, h->Cin,
-                                                                       h->kh * h->kw, h->Cp, h->n_tiles, 0, digits, digit_c);
-    if (hipGetLastError() != hipSuccess) {
-        (void)hipFree(d);
-        return nullptr;
-    }
-    h->dtw_dev = d;
-    h->dtw_digits = digits; h->dtw_c = digit_c;
-    return d;
+        adapt::pack_quad_tables_kernel<<<(unsigned)blocks, 256, 0, s>>>(h->lut->lut16_dev[0], h->w8_dev, h->dtq_dev, h->bits, h->N, h->Cin,
+                                                                       h->kh * h->kw, h->Cp, h->n_tiles, 0, 1, h->dtq_c);
+    HIP_TRY(hipGetLastError());
+    return ADAPT_OK;
 }
 
 // zero-padded activation copy of a convolution's input (int8, or fp32 quantised on the way)
@@ -675,9 +661,10 @@ int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     c.M = M;
     c.phases.resize(1);
     c.out_elems = (size_t)M * q.N; c.out_channels = (size_t)q.N; c.out_inner = 1;
-    const size_t part_bytes = lines_partial_bytes(M, q.n_tiles, q.Cc, 1, c.out_elems);
+    c.plan = plan_product(q, bits, storage, M, 1, M, 1, wh && wh->dtq_dev);
+    const size_t part_bytes = plan_partial_bytes(c.plan, c.out_elems);
     const size_t copy_bytes = (((size_t)M * Kp + 64 + 255) / 256) * 256;
-    if (lines_rows_per_lane(M, q.n_tiles, q.Cc, 1) == 8 && M % 8 == 0) {
+    if (c.plan.xmajor) {
         // x-major copy: one image of one row of M pixels with K channels; a lane's 8 rows x 4 inner indices are 32
         // contiguous bytes instead of 8 words that are a whole matrix row apart
         int wrc = ws_get(ws, copy_bytes + part_bytes, s, (void **)&tmp);
@@ -690,8 +677,7 @@ int lines_linear(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
         c.oy_stride = c.ky_stride = 0; c.ox_stride = c.kx_stride = 4;
         c.xmajor = 1; c.ch_stride = M;
         c.out_plane = 1; c.out_sy = 0; c.out_sx = q.N;
-        c.dt_wide = ensure_wide(wh, s);
-        if (c.dt_wide) { c.wide_digits = wh->dtw_digits; c.wide_c = wh->dtw_c; }
+        if (c.plan.kernel == LK_QUAD) { c.dt_quad = wh->dtq_dev; c.quad_c = wh->dtq_c; }
     } else {
         if (Kp != K || from_f32 || part_bytes) {
             int wrc = ws_get(ws, copy_bytes + part_bytes, s, (void **)&tmp);
@@ -727,10 +713,10 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     // With 8 rows per lane that are 8 consecutive output pixels of a stride-1 convolution, the copy is laid
     // out so that these rows' activations are contiguous (one wide load per lane instead of one per row).
     const int M = N * Ho * Wo;
-    const int xmajor = (lines_rows_per_lane(M, q.n_tiles, q.k_cc(), q.k_taps()) == 8 && Wo % 4 == 0 && M % 8 == 0 && sw == 1 &&
-                        q.k_cc() % 4 == 0) ? 1 : 0;
+    const LinesPlan plan = plan_product(q, bits, storage, M, 1, Wo, sw, wh && wh->dtq_dev);
+    const int xmajor = plan.xmajor;
     const size_t out_elems = (size_t)M * q.N;
-    const size_t part_bytes = lines_partial_bytes(M, q.n_tiles, q.k_cc(), q.k_taps(), out_elems);
+    const size_t part_bytes = plan_partial_bytes(plan, out_elems);
     const size_t copy_bytes = ((xt_bytes + 64 + 255) / 256) * 256;
     int8_t *xt = nullptr;
     {
@@ -751,6 +737,7 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
         }
     }
     LinesCall c;
+    c.plan = plan;
     c.M = M; c.HoWo = Ho * Wo; c.Wo = Wo;
     c.img_stride = (long long)Hp * Wp * Cp;
     c.oy_stride = sh * Wp * Cp; c.ky_stride = dh * Wp * Cp;
@@ -761,8 +748,7 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     c.phases.resize(1);
     c.out_elems = out_elems; c.out_channels = (size_t)q.N; c.out_inner = (size_t)Ho * Wo;
     if (part_bytes) c.partial = reinterpret_cast<int32_t *>(xt + copy_bytes);
-    if (xmajor) c.dt_wide = ensure_wide(wh, s);
-    if (c.dt_wide) { c.wide_digits = wh->dtw_digits; c.wide_c = wh->dtw_c; }
+    if (plan.kernel == LK_QUAD) { c.dt_quad = wh->dtq_dev; c.quad_c = wh->dtq_c; }
     bool finished = false;
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io, true, nullptr, &finished);
     rc = ws_put(ws, xt, s, rc);
@@ -790,9 +776,10 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
     const int Qy = Ho / st, Qx = Wo / st;
     const int M = N * Qy * Qx;
     const size_t xt_bytes = (size_t)N * Hp * Wp * Cp;
-    const int xmajor = (lines_rows_per_lane(M, q.n_tiles * st * st, q.Cc, Ty * Tx) == 8 && Qx % 4 == 0 && M % 8 == 0 && q.Cc % 4 == 0) ? 1 : 0;
+    const LinesPlan plan = plan_product(q, bits, storage, M, st * st, Qx, 1, wh && wh->dtq_dev);
+    const int xmajor = plan.xmajor;
     const size_t out_elems = (size_t)N * q.N * Ho * Wo;
-    const size_t part_bytes = lines_partial_bytes(M, q.n_tiles * st * st, q.Cc, Ty * Tx, out_elems);
+    const size_t part_bytes = plan_partial_bytes(plan, out_elems);
     const size_t copy_bytes = ((xt_bytes + 64 + 255) / 256) * 256;
     int8_t *xt = nullptr;
     if (input_ready) {          // the layer before wrote the copy (adapt_conv_transpose2d_chain_prepare fixed its place and layout)
@@ -807,6 +794,7 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
         if (prc) return ws_put(ws, xt, s, prc);
     }
     LinesCall c;
+    c.plan = plan;
     c.M = M; c.HoWo = Qy * Qx; c.Wo = Qx;
     c.img_stride = (long long)Hp * Wp * Cp;
     c.oy_stride = c.ky_stride = Wp * Cp;
@@ -830,8 +818,8 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
     const bool border = Ly > 0 || Lx > 0;       // then the sums are corrected before they can be rescaled
     c.out_elems = out_elems; c.out_channels = (size_t)q.N; c.out_inner = (size_t)Ho * Wo;
     if (part_bytes) c.partial = reinterpret_cast<int32_t *>(xt + copy_bytes);
-    if (xmajor) c.dt_wide = ensure_wide(wh, s);
-    if (c.dt_wide) { c.wide_digits = wh->dtw_digits; c.wide_c = wh->dtw_c; }
+    const bool quad = plan.kernel == LK_QUAD;
+    if (quad) { c.dt_quad = wh->dtq_dev; c.quad_c = wh->dtq_c; }
     const bool chained = io && io->chain.buf;
     if ((border || chained) && out_elems < 0x7fffffffull) {     // the product kernel takes the border terms off where it can; its
         if (border) c.zsum = zsum;                              // chained copy needs the true output position of a phase's pixel
@@ -839,7 +827,7 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
     }
     bool border_done = false, finished = false;
     // a chained copy is written by the wide kernel's epilogue or, for every other kernel, by the pass that rescales afterwards
-    const bool chain_ok_in_kernel = !chained || (xmajor && c.dt_wide && storage == 0 && part_bytes == 0 && out_elems < 0x7fffffffull);
+    const bool chain_ok_in_kernel = !chained || (quad && part_bytes == 0 && out_elems < 0x7fffffffull);
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io, !border && chain_ok_in_kernel, &border_done, &finished);
     rc = ws_put(ws, xt, s, rc);
     if (rc != ADAPT_OK) return rc;
@@ -1055,6 +1043,24 @@ int adapt_approx_conv_transpose2d(const adapt_lut *lut, const int8_t *x_dev, con
 
 /* ------------------------------------------------------------------ pre-packed weights */
 
+// A linear handle [G Hs][Hs] with G = 4, 3 or 1, even Hs and a single-pass table can serve recurrent time steps
+// (adapt_lstm_step_f32 / adapt_gru_step_f32 / adapt_rnn_step_f32): row offsets with the columns in cell order (see
+// adapt::RowsParams), from the handle's copy of the weights.
+static int pack_cell_offsets(adapt_weights *h, hipStream_t s, const char *who) {
+    const int Hs = h->Cin;
+    if (h->storage != 0 || Hs % 2 != 0 || h->N % Hs != 0) return ADAPT_OK;
+    const int G = h->N / Hs;
+    if (G != 4 && G != 3 && G != 1) return ADAPT_OK;
+    const size_t n = (size_t)Hs * G * Hs;
+    HIP_TRY(dbg_malloc((void **)&h->wofs_cell_dev, n * sizeof(uint32_t)));
+    h->cell_G = G;
+    adapt::pack_row_offsets_cell_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(h->w8_dev, h->wofs_cell_dev, Hs, G, 1 << (h->bits - 1),
+                                                                                  (1 << h->bits) - 1, h->lut->rs * 2);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ADAPT_ERR_HIP, "%s: pack launch: %s", who, hipGetErrorString(e));
+    return ADAPT_OK;
+}
+
 static int weights_pack(adapt_weights **out, const adapt_lut *lut, const int8_t *w_dev, int kind, int N, int Cin, int kh,
                         int kw, void *stream, const char *who) {
     if (!out) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: out is NULL", who);
@@ -1074,7 +1080,7 @@ static int weights_pack(adapt_weights **out, const adapt_lut *lut, const int8_t 
     h->dt_bytes = q.dt_bytes;
     h->dt_dev[0] = h->dt_dev[1] = nullptr;
     h->stride = 1; h->phased = false; h->zsum_dev = nullptr; h->w8_dev = nullptr; h->lut = lut;
-    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0; h->dtw_dev = nullptr; h->dtw_digits = 0; h->dtw_c = 0; h->wofs_cell_dev = nullptr;
+    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0; h->dtq_dev = nullptr; h->dtq_c = 0; h->dtq_bytes = 0; h->wofs_cell_dev = nullptr; h->cell_G = 0;
     {   // copy of the weights (for table orders made later)
         const size_t wbytes = (size_t)N * Cin * kh * kw;
         hipError_t e = dbg_malloc((void **)&h->w8_dev, wbytes);
@@ -1106,6 +1112,8 @@ static int weights_pack(adapt_weights **out, const adapt_lut *lut, const int8_t 
         }
     }
     rc = pack_lines(lut, w_dev, q, h->dt_dev, (hipStream_t)stream);
+    if (rc == ADAPT_OK) rc = pack_quad(h, (hipStream_t)stream, who);
+    if (rc == ADAPT_OK && kind == 0) rc = pack_cell_offsets(h, (hipStream_t)stream, who);
     if (rc != ADAPT_OK) {
         adapt_weights_destroy(h);
         return rc;
@@ -1156,7 +1164,7 @@ int adapt_weights_pack_conv_transpose2d(adapt_weights **out, const adapt_lut *lu
     h->Cp = h->Cc = h->n_tiles = 0; h->dt_bytes = 0; h->pair_g = 0;
     h->dt_dev[0] = h->dt_dev[1] = nullptr;
     h->zsum_dev = nullptr; h->w8_dev = nullptr; h->lut = lut;
-    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0; h->dtw_dev = nullptr; h->dtw_digits = 0; h->dtw_c = 0; h->wofs_cell_dev = nullptr;
+    h->wofs_dev = nullptr; h->wofs_npad = 0; h->wofs1_dev = nullptr; h->wofs1_npad = 0; h->dtq_dev = nullptr; h->dtq_c = 0; h->dtq_bytes = 0; h->wofs_cell_dev = nullptr; h->cell_G = 0;
     h->phased = kh % stride == 0 && kw % stride == 0 && stride <= 8;
     const size_t wbytes = (size_t)Cout * Cin * kh * kw;
     hipError_t e = dbg_malloc((void **)&h->w8_dev, wbytes);
@@ -1186,6 +1194,7 @@ int adapt_weights_pack_conv_transpose2d(adapt_weights **out, const adapt_lut *lu
             for (int half = 0; half <= lut->storage && e == hipSuccess; ++half) e = dbg_malloc((void **)&h->dt_dev[half], all);
             if (e == hipSuccess) {
                 rc = pack_convt(lut, w_dev, q, kh, kw, stride, h->dt_dev, h->zsum_dev, (hipStream_t)stream);
+                if (rc == ADAPT_OK) rc = pack_quad(h, (hipStream_t)stream, who);
                 if (rc != ADAPT_OK) {
                     adapt_weights_destroy(h);
                     return rc;
@@ -1208,7 +1217,7 @@ int adapt_weights_destroy(adapt_weights *h) {
     if (h->ws.ptr) (void)hipFree(h->ws.ptr);
     if (h->wofs_dev) (void)hipFree(h->wofs_dev);
     if (h->wofs1_dev) (void)hipFree(h->wofs1_dev);
-    if (h->dtw_dev) (void)hipFree(h->dtw_dev);
+    if (h->dtq_dev) (void)hipFree(h->dtq_dev);
     if (h->wofs_cell_dev) (void)hipFree(h->wofs_cell_dev);
     if (h->zsum_dev) (void)hipFree(h->zsum_dev);
     if (h->w8_dev) (void)hipFree(h->w8_dev);
@@ -1403,11 +1412,11 @@ int adapt_conv2d_chain_prepare(const adapt_weights *h, int N, int H, int W, int 
     // the layout decisions of lines_conv2d
     const LinesShape q = shape_of(h);
     const int M = (int)(N * g.Ho * g.Wo);
-    const int xmajor = (lines_rows_per_lane(M, q.n_tiles, q.k_cc(), q.k_taps()) == 8 && g.Wo % 4 == 0 && M % 8 == 0 && stride_w == 1 &&
-                        q.k_cc() % 4 == 0) ? 1 : 0;
+    const LinesPlan plan = plan_product(q, h->bits, h->storage, M, 1, (int)g.Wo, stride_w, h->dtq_dev != nullptr);
+    const int xmajor = plan.xmajor;
     const size_t xt_bytes = (size_t)N * (H + 2 * pad_h) * (W + 2 * pad_w) * q.Cp;
     const size_t copy_bytes = ((xt_bytes + 64 + 255) / 256) * 256;
-    const size_t part_bytes = lines_partial_bytes(M, q.n_tiles, q.k_cc(), q.k_taps(), (size_t)M * q.N);
+    const size_t part_bytes = plan_partial_bytes(plan, (size_t)M * q.N);
     int8_t *xt = nullptr;
     if ((rc = ws_get(&h->ws, copy_bytes + part_bytes, (hipStream_t)stream, (void **)&xt))) return rc;
     adapt::fill_u32_kernel<<<ew_grid(copy_bytes / 4), 256, 0, (hipStream_t)stream>>>(reinterpret_cast<uint32_t *>(xt), 0u, copy_bytes / 4);
@@ -1521,10 +1530,11 @@ int adapt_conv_transpose2d_chain_prepare(const adapt_weights *h, int N, int H, i
     // the layout decisions of lines_conv_transpose2d
     const int st = h->stride, Ty = q.kh, Tx = q.kw;
     const int Qy = (int)(Ho / st), Qx = (int)(Wo / st), M = N * Qy * Qx;
-    const int xmajor = (lines_rows_per_lane(M, q.n_tiles * st * st, q.Cc, Ty * Tx) == 8 && Qx % 4 == 0 && M % 8 == 0 && q.Cc % 4 == 0) ? 1 : 0;
+    const LinesPlan plan = plan_product(q, h->bits, h->storage, M, st * st, Qx, 1, h->dtq_dev != nullptr);
+    const int xmajor = plan.xmajor;
     const size_t xt_bytes = (size_t)N * (H + 2 * (Ty - 1)) * (W + 2 * (Tx - 1)) * q.Cp;
     const size_t copy_bytes = ((xt_bytes + 64 + 255) / 256) * 256;
-    const size_t part_bytes = lines_partial_bytes(M, q.n_tiles * st * st, q.Cc, Ty * Tx, (size_t)N * q.N * Ho * Wo);
+    const size_t part_bytes = plan_partial_bytes(plan, (size_t)N * q.N * Ho * Wo);
     int8_t *xt = nullptr;
     if ((rc = ws_get(&h->ws, copy_bytes + part_bytes, (hipStream_t)stream, (void **)&xt))) return rc;
     adapt::fill_u32_kernel<<<ew_grid(copy_bytes / 4), 256, 0, (hipStream_t)stream>>>(reinterpret_cast<uint32_t *>(xt), 0u, copy_bytes / 4);
@@ -1590,24 +1600,6 @@ int adapt_conv_transpose2d_layer_chain_f32(const adapt_weights *h, const float *
 
 /* ------------------------------------------------------------------ LSTM time step in one kernel */
 
-// first use of a [G Hs][Hs] handle for time steps: row offsets with the columns in cell order (see adapt::RowsParams),
-// from the handle's copy of the weights
-static int ensure_cell_offsets(const adapt_weights *h, int Hs, int G, hipStream_t s, const char *who) {
-    if (h->wofs_cell_dev) return ADAPT_OK;
-    const size_t n = (size_t)Hs * G * Hs;
-    uint32_t *d = nullptr;
-    HIP_TRY(dbg_malloc((void **)&d, n * sizeof(uint32_t)));
-    adapt::pack_row_offsets_cell_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(h->w8_dev, d, Hs, G, 1 << (h->bits - 1),
-                                                                                  (1 << h->bits) - 1, h->lut->rs * 2);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) {
-        (void)hipFree(d);
-        return fail(ADAPT_ERR_HIP, "%s: pack launch: %s", who, hipGetErrorString(e));
-    }
-    h->wofs_cell_dev = d;
-    return ADAPT_OK;
-}
-
 int adapt_lstm_step_f32(const adapt_weights *h, const int8_t *qh_dev, const int32_t *acc_ih_dev, float s_ih, float s_hh, float s_h,
                         const float *bias_dev, float *c_dev, float *h_dev, int8_t *qh_next_dev, int B, int Hs, void *stream) {
     const char *who = "adapt_lstm_step_f32";
@@ -1621,7 +1613,7 @@ int adapt_lstm_step_f32(const adapt_weights *h, const int8_t *qh_dev, const int3
     if (h->storage != 0 || Hs % 2 != 0 || (long long)B * 4 * Hs > 0x7fffffffLL)
         return fail(ADAPT_ERR_UNSUPPORTED, "%s: shape outside the fused kernel (Hs even, single-pass table)", who);
     hipStream_t s = (hipStream_t)stream;
-    if ((rc = ensure_cell_offsets(h, Hs, 4, s, who))) return rc;
+    if (!h->wofs_cell_dev || h->cell_G != 4) return fail(ADAPT_ERR_UNSUPPORTED, "%s: the handle holds no cell-order offsets", who);
     Geometry g{};
     g.mode = adapt::MODE_GEMM; g.M = B; g.N = 4 * Hs; g.Cin = Hs; g.taps = 1; g.kw = 1;
     g.H = 1; g.W = 1; g.Wo = 1; g.HoWo = 1; g.sh = g.sw = g.dh = g.dw = 1; g.ph = g.pw = 0;
@@ -1646,7 +1638,7 @@ int adapt_gru_step_f32(const adapt_weights *h, const int8_t *qh_dev, const int32
     if (h->storage != 0 || Hs % 2 != 0 || (long long)B * 3 * Hs > 0x7fffffffLL)
         return fail(ADAPT_ERR_UNSUPPORTED, "%s: shape outside the fused kernel (Hs even, single-pass table)", who);
     hipStream_t s = (hipStream_t)stream;
-    if ((rc = ensure_cell_offsets(h, Hs, 3, s, who))) return rc;
+    if (!h->wofs_cell_dev || h->cell_G != 3) return fail(ADAPT_ERR_UNSUPPORTED, "%s: the handle holds no cell-order offsets", who);
     Geometry g{};
     g.mode = adapt::MODE_GEMM; g.M = B; g.N = 3 * Hs; g.Cin = Hs; g.taps = 1; g.kw = 1;
     g.H = 1; g.W = 1; g.Wo = 1; g.HoWo = 1; g.sh = g.sw = g.dh = g.dw = 1; g.ph = g.pw = 0;
@@ -1672,7 +1664,7 @@ int adapt_rnn_step_f32(const adapt_weights *h, const int8_t *qh_dev, const int32
     if (h->storage != 0 || Hs % 2 != 0 || (long long)B * Hs > 0x7fffffffLL)
         return fail(ADAPT_ERR_UNSUPPORTED, "%s: shape outside the fused kernel (Hs even, single-pass table)", who);
     hipStream_t s = (hipStream_t)stream;
-    if ((rc = ensure_cell_offsets(h, Hs, 1, s, who))) return rc;
+    if (!h->wofs_cell_dev || h->cell_G != 1) return fail(ADAPT_ERR_UNSUPPORTED, "%s: the handle holds no cell-order offsets", who);
     Geometry g{};
     g.mode = adapt::MODE_GEMM; g.M = B; g.N = Hs; g.Cin = Hs; g.taps = 1; g.kw = 1;
     g.H = 1; g.W = 1; g.Wo = 1; g.HoWo = 1; g.sh = g.sw = g.dh = g.dw = 1; g.ph = g.pw = 0;

@@ -256,7 +256,7 @@ static __global__ __launch_bounds__(EW_THREADS) void add_kernel(const float *a, 
 }
 
 // gradient through the fused ReLU: dx = dy where the layer's output y is positive
-static __global__ __launch_bounds__(EW_THREADS) void relu_backward_kernel(const float *__restrict__ dy, const float *__restrict__ y, float *__restrict__ dx, size_t n) {
+static __global__ __launch_bounds__(EW_THREADS) void relu_backward_kernel(const float *dy, const float *__restrict__ y, float *dx, size_t n) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
     for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) dx[i] = y[i] > 0.0f ? dy[i] : 0.0f;
 }
