@@ -120,9 +120,11 @@ struct LstmStep {            // see adapt::RowsParams
     float s_ih, s_hh, s_h, Qh;
 };
 
+// pack_into: room for Ktot * (N rounded up to 16) * groups row offsets that the call may use instead of a stream-ordered
+// temporary (then it allocates nothing)
 int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *out, const Geometry &g, hipStream_t s,
              const uint32_t *prepacked = nullptr, int prepacked_npad = 0, const LayerIO *io = nullptr,
-             const LstmStep *lstm = nullptr) {
+             const LstmStep *lstm = nullptr, uint32_t *pack_into = nullptr) {
     const int bits = lut->bits;
     const long long Ktot = (long long)g.taps * g.Cin;
     const int ngroups = g.groups > 1 ? g.groups : 1;
@@ -146,7 +148,8 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
     uint32_t *wofs = nullptr;
     int rc = ADAPT_OK;
     if (!prepacked) {
-        HIP_TRY(dbg_malloc_async((void **)&wofs, (size_t)Ktot * Npad * ngroups * sizeof(uint32_t), s));
+        if (pack_into) wofs = pack_into;
+        else HIP_TRY(dbg_malloc_async((void **)&wofs, (size_t)Ktot * Npad * ngroups * sizeof(uint32_t), s));
         const size_t pack_n = (size_t)Ktot * Npad;
         adapt::pack_row_offsets_kernel<<<dim3((unsigned)((pack_n + 255) / 256), (unsigned)ngroups), 256, 0, s>>>(
             w, wofs, (int)Ktot, g.N, Npad, g.Cin, g.taps, g.wt ? (int)adapt::MODE_CONVT : g.mode, 1 << (bits - 1), (1 << bits) - 1,
@@ -189,7 +192,7 @@ int run_rows(const adapt_lut *lut, const int8_t *x, const int8_t *w, int32_t *ou
         else if (NT == 2) rc = launch_rows_inst<2, true>(p, grid, lds, s);      // (plain recurrent step, likewise)
         else rc = sgn ? launch_rows_inst<8, true>(p, grid, lds, s) : launch_rows_inst<8, false>(p, grid, lds, s);
     }
-    if (wofs) {
+    if (wofs && !pack_into) {
         hipError_t fe = hipFreeAsync(wofs, s);
         if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
     }
@@ -369,20 +372,6 @@ int launch_lines_xmajor(const adapt::LinesParams &p, unsigned grid, hipStream_t 
 // border terms of a transposed convolution off, knows tanh and writes the next layer's input copy
 template <int DOPS, int R>
 int launch_quad_inst(const adapt::LinesParams &p, unsigned grid, bool extra, hipStream_t s) {
-    // The kernel's table buffers must start at LDS address 0 (its address arithmetic puts the buffer number into bits
-    // 16 and up): true as long as they are the kernel's only LDS object, which its LDS size tells.
-    static std::atomic<int> checked{0};
-    if (!checked.load(std::memory_order_acquire)) {
-        for (int e = 0; e < 2; ++e) {
-            hipFuncAttributes fa;
-            const void *fn = e ? reinterpret_cast<const void *>(adapt::lut_quad_kernel<DOPS, R, true>)
-                               : reinterpret_cast<const void *>(adapt::lut_quad_kernel<DOPS, R, false>);
-            HIP_TRY(hipFuncGetAttributes(&fa, fn));
-            if (fa.sharedSizeBytes != (size_t)2 * adapt::QUAD_BUF_BYTES)
-                return fail(ADAPT_ERR_HIP, "quad kernel: %zu bytes of LDS instead of the two table buffers alone", (size_t)fa.sharedSizeBytes);
-        }
-        checked.store(1, std::memory_order_release);
-    }
     if (extra) adapt::lut_quad_kernel<DOPS, R, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
     else adapt::lut_quad_kernel<DOPS, R, false><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
     HIP_TRY(hipGetLastError());

@@ -160,7 +160,9 @@ __device__ __forceinline__ void quad_add(i32x4_t &d, u32x4_t &v, const i32x4_t &
 template <int DOPS, int R, bool EXTRA>
 __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesParams p) {
     static_assert(R == 8 || R == 4 || R == 2, "rows per row slot");
-    __shared__ __attribute__((aligned(256))) uint4 tbl[2 * (QUAD_BUF_BYTES / 16)];      // 128 KB, the only LDS object
+    // 128 KB; the alignment makes the LDS layout put the buffers at multiples of 64 KB, which the address arithmetic
+    // below relies on (the buffer number sits in bits 16 and up of a line address)
+    __shared__ __attribute__((aligned(QUAD_BUF_BYTES))) uint4 tbl[2 * (QUAD_BUF_BYTES / 16)];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -183,8 +185,6 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
     const int nsteps = min(steps_all, s_begin + p.gps) - s_begin;
     const unsigned char *dt = reinterpret_cast<const unsigned char *>(p.dt) + ((size_t)pick4(p.dt_off, ph) << 4) +
                               ((size_t)nt * steps_all + s_begin) * table_bytes;
-    // the address arithmetic below needs the buffers at multiples of 64 KB: tbl is the kernel's only LDS object and
-    // therefore sits at address 0 (the host checks the kernel's LDS size before the first launch)
     const uint32_t lds_tbl = (uint32_t)(uintptr_t)(lds_void_ptr)tbl;
 
     // table copy: operation o of wave w moves the 1 KB chunk (o * 16 + w); tables below 16 KB use part of the lanes
