@@ -128,6 +128,18 @@ int adapt_mse_from_histogram(const uint32_t *counts_dev, int bins, float amax, i
 int adapt_approx_linear(const adapt_lut *lut, const int8_t *a_dev, const int8_t *w_dev, int32_t *acc_dev,
                         int M, int K, int N, void *stream);
 
+/* adapt_approx_linear for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same integers.  The call makes no allocation of any kind (no
+ * hipMalloc / hipMallocAsync / hipFree, also none hidden in a library routine): the row offsets it derives from w_dev
+ * live in a static device array of 4 MiB that is part of the library's code object (each GPU the library runs on holds
+ * it until the process ends; the first call on a device looks its address up).  Limit: K * (N rounded up to a multiple
+ * of 16) * 4 bytes <= 4 MiB (e.g. K = N = 1024), beyond that ADAPT_ERR_UNSUPPORTED and nothing is launched.  Every
+ * shape runs on the whole-table kernel (long matrices are faster through adapt_approx_linear or a packed handle).
+ * All calls on one GPU share that array: two calls that overlap in time on one GPU (different streams or threads) race;
+ * calls on one stream are ordered.  Nothing in the array has to start at zero (every call rewrites what it reads). */
+int adapt_approx_linear_noalloc(const adapt_lut *lut, const int8_t *a_dev, const int8_t *w_dev, int32_t *acc_dev,
+                                int M, int K, int N, void *stream);
+
 /* 2-D convolution, x NCHW [N][Cin][H][W], w [Cout][Cin/groups][kh][kw], acc [N][Cout][Hout][Wout],
  * Hout = (H + 2 pad_h - dil_h (kh-1) - 1) / stride_h + 1 (likewise Wout).  The layer is the product of
  * the expanded input matrix with the filter matrix (Sec. III-B); a tap that falls into the padding is

@@ -25,7 +25,7 @@ EXPORTS = [
     "adapt_absmax_f32", "adapt_quantize_f32", "adapt_dequant_i32",
     "adapt_absmax_rows_f32", "adapt_quantize_rows_f32", "adapt_dequant_i32_per_channel",
     "adapt_histogram_abs_f32", "adapt_percentile_from_histogram", "adapt_mse_from_histogram",
-    "adapt_approx_linear", "adapt_approx_conv2d", "adapt_approx_conv_transpose2d",
+    "adapt_approx_linear", "adapt_approx_linear_noalloc", "adapt_approx_conv2d", "adapt_approx_conv_transpose2d",
     "adapt_weights_pack_linear", "adapt_weights_pack_conv2d", "adapt_weights_pack_conv_transpose2d",
     "adapt_weights_destroy",
     "adapt_approx_linear_packed", "adapt_approx_conv2d_packed", "adapt_approx_conv_transpose2d_packed",
@@ -85,6 +85,7 @@ def load() -> ctypes.CDLL:
     L.adapt_approx_conv2d_func_i16.argtypes = [i32, i32, i32, vp, vp, vp] + [i32] * 13 + [vp]
     L.adapt_dequant_i32.argtypes = [vp, vp, sz, sz, sz, f32, vp, vp]
     L.adapt_approx_linear.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
+    L.adapt_approx_linear_noalloc.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
     L.adapt_approx_conv2d.argtypes = [vp, vp, vp, vp] + [i32] * 14 + [vp]
     L.adapt_approx_conv_transpose2d.argtypes = [vp, vp, vp, vp] + [i32] * 9 + [vp]
     L.adapt_weights_pack_linear.argtypes = [ctypes.POINTER(vp), vp, vp, i32, i32, vp]
@@ -315,6 +316,16 @@ def adapt_approx_linear(lut: Lut, a, w, out=None, stream=None):
         out = torch.empty((M, N), dtype=torch.int32, device=a.device)
     _chk(load().adapt_approx_linear(lut.handle, _ptr(a, torch.int8), _ptr(w, torch.int8), _ptr(out, torch.int32),
                                     M, K, N, _stream(stream)))
+    return out
+
+
+def adapt_approx_linear_noalloc(lut: Lut, a, w, out, stream=None):
+    """The entry point that allocates nothing: `out` ([M][N] int32) is the caller's, as everything else."""
+    M, K = a.shape
+    N, K2 = w.shape
+    assert K == K2 and tuple(out.shape) == (M, N)
+    _chk(load().adapt_approx_linear_noalloc(lut.handle, _ptr(a, torch.int8), _ptr(w, torch.int8), _ptr(out, torch.int32),
+                                            M, K, N, _stream(stream)))
     return out
 
 

@@ -1,6 +1,8 @@
 // C ABI, part 2: the table-lookup products (linear, convolution, transposed convolution), packed weights, whole-layer
 // calls, chained layers and recurrent time steps.  All arithmetic of the path runs in the kernels included below;
 // nothing here falls back to host computation.
+#include <mutex>
+
 #include "api_common.hpp"
 #include "lut_lines.hpp"
 #include "lut_quad.hpp"
@@ -78,7 +80,29 @@ struct adapt_weights {
 
 /* ------------------------------------------------------------------ table-lookup matrix products */
 
+// Scratch of the entry point that allocates nothing (adapt_approx_linear_noalloc): the row offsets of one call.  One
+// array per GPU, part of the loaded code object, held until the process ends.  Host code never uses the array's name as
+// an address: noalloc_scratch() asks the runtime for the device address once per device and hands that out.
+constexpr size_t NOALLOC_SCRATCH_BYTES = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+
 namespace {
+
+int noalloc_scratch(void **out, const char *who) {
+    static std::mutex mu;
+    static void *ptr[64] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return fail(ADAPT_ERR_HIP, "%s: hipGetDevice failed", who);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));    // the current device's copy of the array
+        if (e != hipSuccess || !p) return fail(ADAPT_ERR_HIP, "%s: hipGetSymbolAddress(scratch): %s", who, hipGetErrorString(e));
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return ADAPT_OK;
+}
 
 template <int NT, bool SIGNED>
 int launch_rows_inst(const adapt::RowsParams &p, dim3 grid, size_t lds, hipStream_t s) {
@@ -972,6 +996,29 @@ int adapt_approx_linear(const adapt_lut *lut, const int8_t *a_dev, const int8_t 
             });
     }
     return run_rows(lut, a_dev, w_dev, acc_dev, g, (hipStream_t)stream);
+}
+
+int adapt_approx_linear_noalloc(const adapt_lut *lut, const int8_t *a_dev, const int8_t *w_dev, int32_t *acc_dev, int M, int K, int N,
+                                void *stream) {
+    const char *who = "adapt_approx_linear_noalloc";
+    int rc = check_lut(lut, who);
+    if (rc) return rc;
+    if (M < 0 || K < 0 || N < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: negative dimension", who);
+    if (M == 0 || N == 0) return ADAPT_OK;
+    if (!acc_dev || (K > 0 && (!a_dev || !w_dev))) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
+    if ((long long)M * N > 0x7fffffffLL || (long long)M * K > 0x7fffffffLL || (long long)N * K > 0x7fffffffLL)
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
+    const long long need = (long long)K * (((long long)N + 15) / 16 * 16) * (long long)sizeof(uint32_t);
+    if (need > (long long)NOALLOC_SCRATCH_BYTES)
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: K * (N rounded up to 16) * 4 = %lld bytes of row offsets exceed the %zu bytes of static scratch",
+                    who, need, NOALLOC_SCRATCH_BYTES);
+    void *scr = nullptr;
+    if ((rc = noalloc_scratch(&scr, who))) return rc;
+    Geometry g{};
+    g.mode = adapt::MODE_GEMM; g.M = M; g.N = N; g.Cin = K; g.taps = 1; g.kw = 1;
+    g.H = 1; g.W = 1; g.Wo = 1; g.HoWo = 1; g.sh = g.sw = g.dh = g.dw = 1; g.ph = g.pw = 0;
+    g.kstride = 1; g.img_stride = K;
+    return run_rows(lut, a_dev, w_dev, acc_dev, g, (hipStream_t)stream, nullptr, 0, nullptr, nullptr, static_cast<uint32_t *>(scr));
 }
 
 int adapt_approx_conv2d(const adapt_lut *lut, const int8_t *x_dev, const int8_t *w_dev, int32_t *acc_dev, int N,
