@@ -187,6 +187,19 @@ int adapt_weights_pack_conv_transpose2d(adapt_weights **out, const adapt_lut *lu
                                         int kh, int kw, int stride, void *stream);
 int adapt_weights_destroy(adapt_weights *w);
 
+/* Diagnostic, host only (no device call when cu > 0): how a product on a packed handle of this shape is spread over the
+ * chip (Sec. IV: the matrix product is where the time goes, so which kernel runs it and in which launch shape is what a
+ * profile has to be read against).  kind 0 linear (kh = kw = 1), 1 conv2d, 2 transposed conv2d with `stride`; storage as
+ * adapt_lut_info reports it; rows = rows of the product (linear: M; convolution: N Ho Wo; transposed convolution: N Ho Wo
+ * / stride^2, the rows of one phase), Wo = output width of one image row (linear: M; transposed: Wo / stride), sw =
+ * horizontal stride; cu = compute units to plan for (<= 0: those of the current device).
+ * *kernel: -1 whole-table kernel (lut_rows_kernel), 0 lut_lines_kernel, 1 lut_lines_fast_kernel, 2 the same on the
+ * x-major copy, 3 lut_quad_kernel; *rows_per_workgroup; *ksplit = workgroups that share an output tile, each with a slice
+ * of the inner dimension; *steps = table steps of the whole inner dimension (16 inner indices each for kernel 3, 8
+ * otherwise); *workgroups = size of the launch.  Any output pointer may be NULL. */
+int adapt_plan_packed(int kind, int bits, int storage, int Cout, int Cin, int kh, int kw, int stride, int rows, int Wo, int sw, int cu,
+                      int *kernel, int *rows_per_workgroup, int *ksplit, int *steps, int *workgroups);
+
 /* same results as adapt_approx_linear / adapt_approx_conv2d with the weights and table given at pack time */
 int adapt_approx_linear_packed(const adapt_weights *w, const int8_t *a_dev, int32_t *acc_dev, int M, void *stream);
 int adapt_approx_conv2d_packed(const adapt_weights *w, const int8_t *x_dev, int32_t *acc_dev, int N, int H, int W,

@@ -27,7 +27,7 @@ EXPORTS = [
     "adapt_histogram_abs_f32", "adapt_percentile_from_histogram", "adapt_mse_from_histogram",
     "adapt_approx_linear", "adapt_approx_linear_noalloc", "adapt_approx_conv2d", "adapt_approx_conv_transpose2d",
     "adapt_weights_pack_linear", "adapt_weights_pack_conv2d", "adapt_weights_pack_conv_transpose2d",
-    "adapt_weights_destroy",
+    "adapt_weights_destroy", "adapt_plan_packed",
     "adapt_approx_linear_packed", "adapt_approx_conv2d_packed", "adapt_approx_conv_transpose2d_packed",
     "adapt_linear_layer_f32", "adapt_conv2d_layer_f32", "adapt_conv_transpose2d_layer_f32",
     "adapt_conv_transpose2d_chain_prepare", "adapt_conv_transpose2d_layer_chain_f32",
@@ -93,6 +93,7 @@ def load() -> ctypes.CDLL:
     L.adapt_weights_pack_conv_transpose2d.argtypes = [ctypes.POINTER(vp), vp, vp, i32, i32, i32, i32, i32, vp]
     L.adapt_approx_conv_transpose2d_packed.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
     L.adapt_weights_destroy.argtypes = [vp]
+    L.adapt_plan_packed.argtypes = [i32] * 12 + [ctypes.POINTER(i32)] * 5
     L.adapt_linear_layer_f32.argtypes = [vp, vp, vp, i32, f32, f32, vp, vp, i32, vp]
     L.adapt_conv2d_layer_f32.argtypes = [vp, vp, vp] + [i32] * 9 + [f32, f32, vp, vp, vp, i32, vp]
     L.adapt_conv2d_chain_prepare.argtypes = [vp] + [i32] * 9 + [vp]
@@ -317,6 +318,17 @@ def adapt_approx_linear(lut: Lut, a, w, out=None, stream=None):
     _chk(load().adapt_approx_linear(lut.handle, _ptr(a, torch.int8), _ptr(w, torch.int8), _ptr(out, torch.int32),
                                     M, K, N, _stream(stream)))
     return out
+
+
+PLAN_KERNELS = {-1: "lut_rows_kernel", 0: "lut_lines_kernel", 1: "lut_lines_fast_kernel", 2: "lut_lines_fast_kernel (x-major)",
+                3: "lut_quad_kernel"}
+
+
+def adapt_plan_packed(kind, bits, storage, Cout, Cin, kh, kw, stride, rows, Wo, sw, cu=0):
+    """(kernel, rows per workgroup, ksplit, steps, workgroups) of a product on a packed handle of this shape."""
+    out = [ctypes.c_int() for _ in range(5)]
+    _chk(load().adapt_plan_packed(kind, bits, storage, Cout, Cin, kh, kw, stride, rows, Wo, sw, cu, *[ctypes.byref(o) for o in out]))
+    return tuple(o.value for o in out)
 
 
 def adapt_approx_linear_noalloc(lut: Lut, a, w, out, stream=None):

@@ -10,6 +10,9 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libadapt_mi355.so")
 SOURCES = [os.path.join(CSRC, f) for f in ("api_core.hip", "api_layers.hip", "api_i16.hip", "api_backward.hip")]
+# ceiling probes for bench.py: a library of their own, not part of the product
+PROBES_LIB = os.path.join(HERE, "libadapt_probes.so")
+PROBES_SOURCE = os.path.join(CSRC, "probes.hip")
 # translation units whose kernels issue loads from inline assembly (what isa_check.py scans)
 HAND_SCHEDULED = [os.path.join(CSRC, "api_layers.hip")]
 
@@ -44,8 +47,11 @@ def build(force: bool = True, verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJ, exist_ok=True)
     objs = [os.path.join(OBJ, os.path.basename(s)[:-4] + ".o") for s in SOURCES]
-    with ThreadPoolExecutor(max_workers=len(SOURCES)) as pool:
-        list(pool.map(lambda so: _run([hipcc] + HIPCC_FLAGS + ["-c", so[0], "-o", so[1]], verbose), zip(SOURCES, objs)))
+    extra = os.environ.get("ADAPT_EXTRA_HIPCC_FLAGS", "").split()      # e.g. -DADAPT_TUNING_KNOBS for tuning experiments
+    jobs = [[hipcc] + HIPCC_FLAGS + extra + ["-c", src, "-o", obj] for src, obj in zip(SOURCES, objs)]
+    jobs.append([hipcc] + HIPCC_FLAGS + ["-shared", "-o", PROBES_LIB, PROBES_SOURCE])
+    with ThreadPoolExecutor(max_workers=len(jobs)) as pool:
+        list(pool.map(lambda cmd: _run(cmd, verbose), jobs))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, verbose)
     return LIB
 

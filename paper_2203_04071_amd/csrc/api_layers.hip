@@ -411,8 +411,7 @@ int launch_quad_r(const adapt::LinesParams &p, unsigned grid, bool extra, hipStr
 
 int launch_quad(const adapt::LinesParams &p, unsigned grid, int R, bool extra, hipStream_t s) {
     if (R == 8) return launch_quad_r<8>(p, grid, extra, s);
-    if (R == 4) return launch_quad_r<4>(p, grid, extra, s);
-    return launch_quad_r<2>(p, grid, extra, s);
+    return launch_quad_r<4>(p, grid, extra, s);
 }
 
 template <int R>
@@ -489,16 +488,26 @@ struct LinesCall {       // per-call geometry of the activation side
 
 // The plan of one product (see lines_plan.hpp).  M: rows (per phase); phases: 1, or stride^2 of a transposed convolution;
 // Wo: output width (linear layers: M); sw: horizontal stride; quad_tables: the caller holds tables in the quad order.
-LinesPlan plan_product(const LinesShape &q, int bits, int storage, int M, int phases, int Wo, int sw, bool quad_tables) {
+LinesPlan plan_product(const LinesShape &q, int bits, int storage, int M, int phases, int Wo, int sw, bool quad_tables, int cu = 0) {
     PlanIn in;
     in.M = M; in.tiles = q.n_tiles * phases; in.k_cc = q.k_cc(); in.k_taps = q.k_taps(); in.Wo = Wo; in.sw = sw;
     in.quad_steps = (quad_tables && storage == 0 && q.Cp % adapt::QUAD_STEP == 0) ? q.kh * q.kw * (q.Cp / adapt::QUAD_STEP) : 0;
-    in.cu = device_cus();
-    (void)bits;
-    return plan_lines(in);
+    in.bits = bits; in.cu = cu > 0 ? cu : device_cus();
+    LinesPlan pl = plan_lines(in);
+#ifdef ADAPT_TUNING_KNOBS
+    if (const char *e = getenv("ADAPT_QUAD_PLAN")) {        // "R,ksplit": tuning experiments only (not compiled into the product)
+        int R = 0, ks = 0;
+        if (pl.kernel == LK_QUAD && sscanf(e, "%d,%d", &R, &ks) == 2 && quad_rows_ok(R, M, Wo) && ks >= 1 && ks <= in.quad_steps) {
+            const int sps = (in.quad_steps + ks - 1) / ks;
+            pl.R = R; pl.gps = sps; pl.ksplit = (in.quad_steps + sps - 1) / sps;
+        }
+    }
+#endif
+    return pl;
 }
 
-// bytes of partial sums a call needs (0 without a split of the inner dimension)
+// bytes of partial sums a call needs from its workspace (0 without a split of the inner dimension): ksplit copies of
+// the output for reduce_partials_kernel
 size_t plan_partial_bytes(const LinesPlan &pl, size_t out_elems) {
     return pl.ksplit > 1 ? (size_t)pl.ksplit * out_elems * sizeof(int32_t) : 0;
 }
@@ -516,8 +525,8 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     const int R = pl.R;
     const bool quad = pl.kernel == LK_QUAD;
     const bool split = pl.ksplit > 1;
-    if (split && !c.partial) return fail(ADAPT_ERR_HIP, "lines path: no room for partial sums");
-    if (quad && (!c.dt_quad || storage != 0 || !c.xmajor)) return fail(ADAPT_ERR_HIP, "lines path: quad plan without quad tables");
+    const bool sums_elsewhere = split;      // partial sums in c.partial, added by reduce_partials_kernel
+    if (sums_elsewhere && !c.partial) return fail(ADAPT_ERR_HIP, "lines path: no room for partial sums");
     adapt::LinesParams p;
     p.xt = xt;
     p.M = c.M; p.N = q.N; p.n_tiles = q.n_tiles;
@@ -531,7 +540,7 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     p.m_tiles = (c.M + pl.rows_per_wg() - 1) / pl.rows_per_wg();
     p.d_HoWo = fast_div((uint32_t)p.HoWo); p.d_Wo = fast_div((uint32_t)p.Wo);
     p.d_ntiles = fast_div((uint32_t)p.n_tiles); p.d_mtiles = fast_div((uint32_t)p.m_tiles); p.d_phases = fast_div(1u);
-    p.ksplit = pl.ksplit; p.gps = pl.gps; p.ks_out_stride = split ? (long long)c.out_elems : 0;
+    p.ksplit = pl.ksplit; p.gps = pl.gps; p.ks_out_stride = sums_elsewhere ? (long long)c.out_elems : 0;
     // digit tables: every real lookup of an output lacks the offset (sums wrap in 32 bits like everything else)
     p.corr = quad ? (int)(uint32_t)((unsigned long long)((long long)q.kh * q.kw * q.Cin * (long long)c.quad_c)) : 0;
     // one base offset per lane is enough when the R rows of a lane are equally spaced in xt
@@ -540,12 +549,12 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     if (c.xmajor != pl.xmajor) return fail(ADAPT_ERR_HIP, "lines path: the activation copy does not have the layout of the plan");
     // the quad kernel has an instantiation that takes the border terms of a transposed convolution off itself and
     // knows tanh; the kernel that adds split sums knows tanh too
-    const bool border_in_kernel = c.zsum && !split && quad;
+    const bool border_in_kernel = c.zsum && !sums_elsewhere && quad;
     if (border_done) *border_done = border_in_kernel;
-    const bool act_ok = io && (io->act <= 1 || (io->act == 2 && (split || quad)));
+    const bool act_ok = io && (io->act <= 1 || (io->act == 2 && (sums_elsewhere || quad)));
     const bool fuse = (may_fuse || border_in_kernel) && io && io->deq && storage == 0 && act_ok;
     if (finished) *finished = fuse;
-    const bool fuse_in_kernel = fuse && !split;
+    const bool fuse_in_kernel = fuse && !sums_elsewhere;
     const bool chain_in_kernel = fuse_in_kernel && io->chain.buf;
     const bool extra = quad && (border_in_kernel || (fuse_in_kernel && io->act == 2) || chain_in_kernel);
     p.chain = chain_in_kernel ? io->chain : adapt::ChainOut{};
@@ -561,8 +570,8 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     int rc = ADAPT_OK;
     for (int half = 0; half <= storage && rc == ADAPT_OK; ++half) {
         p.dt = quad ? c.dt_quad : dt[half];
-        p.out = split ? c.partial : out;
-        p.shift = (half == 0 || split) ? -1 : 16;
+        p.out = sums_elsewhere ? c.partial : out;
+        p.shift = (half == 0 || sums_elsewhere) ? -1 : 16;
         const bool sgn = storage == 0 || half == 1;
         for (int first = 0; first < n_phases && rc == ADAPT_OK; first += 4) {       // up to four phases per launch
             p.phases = n_phases - first < 4 ? n_phases - first : 4;
@@ -580,7 +589,7 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
             else if (R == 4) rc = launch_lines_r<4>(p, (unsigned)grid, sgn, regular, s);
             else rc = launch_lines_r<2>(p, (unsigned)grid, sgn, regular, s);
         }
-        if (split && rc == ADAPT_OK) {
+        if (sums_elsewhere && rc == ADAPT_OK) {
             const int wo = io ? io->chain_wo : 1;
             const bool chained = fuse && half == 0 && io->chain.buf;
             // four elements per thread where planes (and, with a chained copy, rows) are whole quads and everything is aligned
@@ -1282,6 +1291,35 @@ int adapt_approx_conv_transpose2d_packed(const adapt_weights *h, const int8_t *x
     }
     // geometries outside the phase form (a single input pixel, output sizes that are no multiple of the stride)
     return convt_rows(h->lut, x_dev, h->w8_dev, acc_dev, N, h->Cin, H, W, h->N, h->kh, h->kw, h->stride, pad, (hipStream_t)stream, h);
+}
+
+int adapt_plan_packed(int kind, int bits, int storage, int Cout, int Cin, int kh, int kw, int stride, int rows, int Wo, int sw, int cu,
+                      int *kernel, int *rows_per_workgroup, int *ksplit, int *steps, int *workgroups) {
+    const char *who = "adapt_plan_packed";
+    if (kind < 0 || kind > 2 || bits < 2 || bits > 8 || storage < 0 || storage > 1 || Cout < 1 || Cin < 1 || kh < 1 || kw < 1 || stride < 1 ||
+        rows < 1 || Wo < 1 || sw < 1)
+        return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad argument", who);
+    int k = 0, rpw = 0, ks = 1, st = 0, wg = 0;
+    const bool phased = kind == 2 && kh % stride == 0 && kw % stride == 0;
+    if (rows < LINES_MIN_ROWS && kind == 0) {
+        k = -1;                                 // whole-table kernel (lut_rows_kernel)
+    } else if (kind == 2 && !phased) {
+        k = -1;
+    } else {
+        const LinesShape q = kind == 2 ? convt_phase_shape(bits, Cout, Cin, kh, kw, stride) : lines_shape(kind, bits, Cout, Cin, kh, kw, storage == 0);
+        const int phases = kind == 2 ? stride * stride : 1;
+        const bool quad_tables = storage == 0 && q.Cp % adapt::QUAD_STEP == 0;
+        const LinesPlan pl = plan_product(q, bits, storage, rows, phases, Wo, sw, quad_tables, cu > 0 ? cu : 0);
+        k = pl.kernel; rpw = pl.rows_per_wg(); ks = pl.ksplit;
+        st = pl.kernel == LK_QUAD ? q.kh * q.kw * (q.Cp / adapt::QUAD_STEP) : q.k_taps() * q.k_cc();
+        wg = ((rows + rpw - 1) / rpw) * q.n_tiles * phases * ks;
+    }
+    if (kernel) *kernel = k;
+    if (rows_per_workgroup) *rows_per_workgroup = rpw;
+    if (ksplit) *ksplit = ks;
+    if (steps) *steps = st;
+    if (workgroups) *workgroups = wg;
+    return ADAPT_OK;
 }
 
 int adapt_approx_linear_packed(const adapt_weights *h, const int8_t *a_dev, int32_t *acc_dev, int M, void *stream) {

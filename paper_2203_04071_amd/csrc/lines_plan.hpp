@@ -19,6 +19,7 @@ struct PlanIn {
     int Wo;             // output width (a linear layer is one image row of M pixels: Wo = M)
     int sw;             // horizontal stride of the window
     int quad_steps;     // > 0: quad tables exist for this layer; their steps of 16 inner indices (taps x padded channels / 16)
+    int bits;           // operand bits (table lines = 2^bits)
     int cu;             // compute units
 };
 
@@ -31,34 +32,54 @@ struct LinesPlan {
     int rows_per_wg() const { return (kernel == LK_QUAD ? 256 : 128) * R; }
 };
 
-// Quad kernel.  Rows per row slot R: the largest that still gives every compute unit a workgroup, because the table
-// bytes streamed per multiply-accumulate fall with R.  When not even the smallest fills the chip, the inner dimension is
-// split over up to 16 workgroups of at least four steps each (partial sums, added by reduce_partials_kernel).
-// R rows are consecutive pixels of one image row: R = 8 and 4 take runs of four (Wo % 4 == 0), R = 2 pairs.
-inline bool quad_rows_ok(int R, int M, int Wo) {
-    if (R == 2) return M % 2 == 0 && Wo % 2 == 0;
-    return M % R == 0 && Wo % 4 == 0;
+// Quad kernel.  The R = 8 or 4 rows of a row slot are consecutive pixels of one image row, in runs of four.
+inline bool quad_rows_ok(int R, int M, int Wo) { return (R == 8 || R == 4) && M % R == 0 && Wo % 4 == 0; }
+
+// Estimated duration, in clocks, of a quad launch with R rows per row slot; only differences between the candidates
+// matter.  From measurements of whole layers on one MI355X (3 x 3 convolutions of 16 to 256 channels, 8-bit tables), per
+// step of a workgroup: R = 8 about 4460 clocks when every compute unit has a workgroup and 3770 with half of them busy;
+// R = 4 about 2780 - the path that fills LDS and registers (64 KB of table per step whatever R is, plus R x 4 KB of
+// activations, at about 26 bytes per clock) bounds both, so the cost per multiply-accumulate falls as R grows, but so
+// does the number of workgroups (two rows per row slot were measured too: slower everywhere).  Smaller tables (fewer
+// bits) shrink the table part; the LDS reads (32 per lane and step at R = 8) then become the bound.
+inline long long quad_step_clocks(int R, int bits, double busy) {
+    if (bits >= 8) {
+        if (R == 8) return (long long)(3080 + 1380 * busy);
+        return (long long)(2280 + 500 * busy);
+    }
+    const long long lds = R == 8 ? 3040 : 1600;
+    const long long fill = (long long)(((256LL << bits) + 4096LL * R) / 26.0);
+    return lds > fill ? lds : fill;
 }
+
+inline long long quad_cost(int R, int M, int tiles, int steps, int bits, int cu) {
+    const long long wgs = (long long)((M + 256 * R - 1) / (256 * R)) * tiles;
+    const long long full = wgs / cu, rest = wgs % cu;
+    long long c = full * steps * quad_step_clocks(R, bits, 1.0);
+    if (rest) c += steps * quad_step_clocks(R, bits, (double)rest / cu);
+    return c;
+}
+
+// The quad kernel takes a product when its tables exist, the window moves one pixel at a time, the inner dimension has
+// at least QUAD_MIN_STEPS steps and some admissible R gives at least three quarters of the compute units a workgroup
+// (layers below that - few steps, or so few rows that the inner dimension has to be split over workgroups - measured
+// the same or faster on the 128-byte-line kernels inside a network, where a layer's tables arrive cold).
+constexpr int QUAD_MIN_STEPS = 16;
 
 inline LinesPlan plan_lines(const PlanIn &in) {
     const int M = in.M, cu = in.cu;
-    if (in.quad_steps > 0 && in.sw == 1 && (quad_rows_ok(8, M, in.Wo) || quad_rows_ok(4, M, in.Wo) || quad_rows_ok(2, M, in.Wo))) {
-        auto wgs = [&](int r) { return (long long)((M + 256 * r - 1) / (256 * r)) * in.tiles; };
-        const int Rs[3] = {8, 4, 2};
-        for (int R : Rs)
-            if (quad_rows_ok(R, M, in.Wo) && wgs(R) >= cu) return LinesPlan{LK_QUAD, R, 1, in.quad_steps, 1};
+    if (in.quad_steps >= QUAD_MIN_STEPS && in.sw == 1) {
+        LinesPlan best{LK_QUAD, 0, 1, in.quad_steps, 1};
+        long long best_cost = 0;
+        const int Rs[2] = {8, 4};
         for (int R : Rs) {
             if (!quad_rows_ok(R, M, in.Wo)) continue;
-            long long ks = (cu + wgs(R) - 1) / wgs(R);
-            if (ks > in.quad_steps / 4) ks = in.quad_steps / 4;
-            if (ks > 16) ks = 16;
-            if (ks >= 2 && wgs(R) * ks * 4 >= 3LL * cu) {
-                const int sps = (in.quad_steps + (int)ks - 1) / (int)ks;
-                return LinesPlan{LK_QUAD, R, (in.quad_steps + sps - 1) / sps, sps, 1};
-            }
+            const long long wgs = (long long)((M + 256 * R - 1) / (256 * R)) * in.tiles;
+            if (wgs * 4 < 3LL * cu) continue;
+            const long long c = quad_cost(R, M, in.tiles, in.quad_steps, in.bits, cu);
+            if (best.R == 0 || c < best_cost) { best.R = R; best_cost = c; }
         }
-        for (int i = 2; i >= 0; --i)
-            if (quad_rows_ok(Rs[i], M, in.Wo)) return LinesPlan{LK_QUAD, Rs[i], 1, in.quad_steps, 1};
+        if (best.R) return best;
     }
     // 128-byte-line kernels: rows per lane R (a workgroup handles 128 R rows) as large as still gives every compute unit
     // a workgroup.  When even R = 8 leaves three quarters of them idle and the inner dimension is long enough, keep

@@ -25,7 +25,7 @@
 // into the other by LDS-direct loads (no register round trip); every step ends with vmcnt(0) and a barrier.
 //
 // Activations come from the x-major zero-padded copy (see pad_channels_last_kernel), which holds table line indices:
-// the R pixels x 4 channels of a lane and step are R / 4 loads of 16 bytes (R = 2: one of 8).
+// the R pixels x 4 channels of a lane and step are R / 4 loads of 16 bytes.
 #pragma once
 #include "lut_lines.hpp"
 
@@ -152,14 +152,14 @@ __device__ __forceinline__ void quad_add(i32x4_t &d, u32x4_t &v, const i32x4_t &
 }
 
 // DOPS: table copy operations per wave and step = 2^b * 256 B / (16 waves * 1 KB): 4 / 2 / 1 for b = 8 / 7 / <= 6
-// (smaller tables: one operation with fewer lanes).  R: rows (consecutive output pixels) per row slot, 8 / 4 / 2: a
+// (smaller tables: one operation with fewer lanes).  R: rows (consecutive output pixels) per row slot, 8 or 4: a
 // workgroup owns 256 R rows.  EXTRA: the epilogue also knows tanh, the border terms of a transposed convolution and the
 // next layer's quantised input copy.
 // Launch parameters as for the lines kernels, with these readings: Cc = steps per tap (padded channels / 16);
 // gps = steps per slice of the inner dimension (ksplit > 1).
 template <int DOPS, int R, bool EXTRA>
 __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesParams p) {
-    static_assert(R == 8 || R == 4 || R == 2, "rows per row slot");
+    static_assert(R == 8 || R == 4, "rows per row slot");
     // 128 KB; the alignment makes the LDS layout put the buffers at multiples of 64 KB, which the address arithmetic
     // below relies on (the buffer number sits in bits 16 and up of a line address)
     __shared__ __attribute__((aligned(QUAD_BUF_BYTES))) uint4 tbl[2 * (QUAD_BUF_BYTES / 16)];
@@ -235,8 +235,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
             next_run(img, a, b);
         }
     }
-    typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
-    typedef typename std::conditional<R == 2, u32x2_t, u32x4_t>::type ld_t;     // what one load returns
+    typedef u32x4_t ld_t;                   // what one load returns: four pixels x four channels
     struct Acts {
         ld_t v[NL];
         __device__ __forceinline__ uint32_t row(int i) const { return v[i / 4][i % 4]; }
@@ -246,12 +245,16 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
             asm volatile("global_load_dwordx4 %[a0], %[b0], %[xr]\n\tglobal_load_dwordx4 %[a1], %[b1], %[xr]"
                          : [a0] "+v"(a.v[0]), [a1] "+v"(a.v[1])
                          : [b0] "v"(base[0]), [b1] "v"(base[1]), [xr] "s"(xrow));
-        else if constexpr (R == 4)
-            asm volatile("global_load_dwordx4 %[a0], %[b0], %[xr]" : [a0] "+v"(a.v[0]) : [b0] "v"(base[0]), [xr] "s"(xrow));
         else
-            asm volatile("global_load_dwordx2 %[a0], %[b0], %[xr]" : [a0] "+v"(a.v[0]) : [b0] "v"(base[0]), [xr] "s"(xrow));
+            asm volatile("global_load_dwordx4 %[a0], %[b0], %[xr]" : [a0] "+v"(a.v[0]) : [b0] "v"(base[0]), [xr] "s"(xrow));
     };
-    auto step_end = [&]() { asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" : : : "memory"); };
+    // End of a step: this wave's part of the next table has landed (its copy operations were issued BEFORE the step's
+    // activation loads, and a wave's memory operations retire in order, so all but the newest NL are done); the
+    // activation loads stay in flight across the barrier and are waited for where the next step first needs them.
+    auto step_end = [&]() { asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" : : "n"(NL) : "memory"); };
+    // Start of a step, after its copy operations and loads have been issued: the activations requested one step ago
+    // (the oldest NL of the DOPS + 2 NL operations in flight) have arrived.
+    auto acts_ready = [&]() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(DOPS + NL) : "memory"); };
 
     // position of a step's activations: steps per tap = Cc, 16 channels = 4 channel groups of the copy each
     const int tap0 = s_begin / p.Cc;
@@ -315,7 +318,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
     // prologue: table of step 0, activations of step 0
     dma(0, 0);
     load_acts(actA, xt + tapoff + choff);
-    step_end();
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" : : : "memory");
     advance_step();
 
     int s = 0;
@@ -324,6 +327,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
         dma(s + 1, 1);
         load_acts(actB, xt + tapoff + choff);
         advance_step();
+        acts_ready();
         run_step(std::integral_constant<int, 0>{}, actA);
         step_end();
         // odd step: buffer 1; the next step's table goes to buffer 0 (after the last step: the last one again, unused,
@@ -331,9 +335,11 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
         dma(s + 2, 0);
         load_acts(actA, s + 2 < nsteps ? xt + tapoff + choff : xt);
         advance_step();
+        acts_ready();
         run_step(std::integral_constant<int, 1>{}, actB);
         step_end();
     }
+    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");                      // retire what is still in flight
     if (s < nsteps) run_step(std::integral_constant<int, 0>{}, actA);      // odd number of steps: the last one
 
     // the last matrix instructions have to leave the pipe before a vector instruction reads their registers
@@ -351,7 +357,6 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
         for (int c = 0; c < 4; ++c)
             sum[i][c] = (uint32_t)part[c] + (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, part[c]);
     }
-    if (!live) return;                      // no barrier follows
     // Both lanes now hold channels 4 (q % 2) .. + 3 of the row slot's R pixels; lane q < 2 finishes the first half of
     // the pixels, lane q >= 2 the second.
     constexpr int NP = R / 2;               // pixels per lane in the epilogue
@@ -361,12 +366,16 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
 #pragma unroll
     for (int i = 0; i < NP; ++i)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            w[i][c] = half ? sum[NP + i][c] : sum[i][c];
-            if (ks == 0) w[i][c] += (uint32_t)p.corr;       // the offset of the digit form, once per output
-        }
+        for (int c = 0; c < 4; ++c) w[i][c] = half ? sum[NP + i][c] : sum[i][c];
+    if (!live) return;                      // no barrier follows
+    if (ks == 0) {                          // the offset of the digit form, once per output
+#pragma unroll
+        for (int i = 0; i < NP; ++i)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) w[i][c] += (uint32_t)p.corr;
+    }
     int img, a0, b0;
-    row_pos(r0 + NP * half, img, a0, b0);   // (a lane's NP pixels lie in one image row: Wo is a multiple of min(R, 4))
+    row_pos(r0 + NP * half, img, a0, b0);   // (a lane's NP pixels lie in one image row: Wo is a multiple of 4)
     // transposed convolution (EXTRA instantiation, zsum given): the phase's output pixels are (oy, ox + i * out_sx); the
     // taps that lay over the zero border are taken off for the few pixels that touch the border
     int oy = 0, ox = 0;
