@@ -25,21 +25,74 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-LDS_LANES_PER_CLK_PER_CU = 32      # 32 banks x 4 B: one 16-bit gather lane per bank per clock
+LDS_LANES_PER_CLK_PER_CU = 32      # 32 banks x 4 B: one 16-bit gather lane per bank per clock (the model peak named for this path)
 MODEL_CLOCK_GHZ = 2.4
 GATHER_LANES_PER_CLK_PER_CU = 4    # vector memory path: one 64-lane gather instruction per 16 clocks
 MITCHELL_OPS_PER_MAC = 15          # vector instructions per multiply-accumulate counted in the compiled function-form kernel (484 per 32)
 MODEL_CUS = 256
+HBM_PEAK_BYTES_PER_S = 8.0e12      # published HBM3E rate of MI355X
 
-# HBM bytes per launch of the dominant call, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, each
-# scaled by what the same counter reads for a plain 64 MiB copy (--copy-calibration); figures and commands are in
-# profiles/lut_lines_wide_config2.md.  Keyed by config number; None = not measured.
-MEASURED_TRAFFIC_BYTES = {2: (18576 * 2.0 + 8192 * 1.0 + 4646 * 2.0 + 2312 * 1.0) * 1024}
-# the product kernel alone (lut_lines_wide_kernel<4> at configuration 2), same runs
-MEASURED_KERNEL_TRAFFIC_BYTES = {2: (18576 * 2.0 + 8192 * 1.0) * 1024}
-# clocks the matrix pipe of a SIMD is busy per v_mfma_i32_16x16x64_i8 (SQ_VALU_MFMA_BUSY_CYCLES / SQ_INSTS_VALU_MFMA_I8 of
-# that kernel, profiles/lut_lines_wide_config2.md)
-MFMA_16X16X64_CLOCKS = 16
+# HBM traffic of the headline configuration's kernels: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summaries (KiB per
+# dispatch) and the same counters for a plain copy of known size, which they are scaled by (commands inside the file)
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_config2.txt")
+
+
+def read_traffic():
+    """{kernel: HBM bytes per dispatch} from the committed counter summary, or {} when there is none."""
+    vals = {}
+    try:
+        for line in open(TRAFFIC_FILE):
+            line = line.split("#")[0].strip()
+            if "=" in line:
+                k, v = line.split("=", 1)
+                vals[k.strip()] = float(v)
+    except OSError:
+        return {}
+    try:
+        f_scale = vals["copy_kib"] / vals["copy_fetch_kib"]
+        w_scale = vals["copy_kib"] / vals["copy_write_kib"]
+    except (KeyError, ZeroDivisionError):
+        return {}
+    out = {}
+    for k in vals:
+        if k.endswith("_fetch_kib") and not k.startswith("copy_"):
+            name = k[:-len("_fetch_kib")]
+            if name + "_write_kib" in vals:
+                out[name] = (vals[k] * f_scale + vals[name + "_write_kib"] * w_scale) * 1024.0
+    return out
+
+
+def run_probes():
+    """Ceilings measured on this device, right now, by the probe kernels of paper_2203_04071_amd/csrc/probes.hip."""
+    import ctypes
+    from paper_2203_04071_amd import build as hip_build
+    if not os.path.exists(hip_build.PROBES_LIB):
+        return None
+    L = ctypes.CDLL(hip_build.PROBES_LIB)
+    L.adapt_probe_run.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
+
+    def rate(which, iters):
+        ms, units = ctypes.c_float(), ctypes.c_double()
+        for _ in range(2):      # first run also brings the clocks up
+            if L.adapt_probe_run(which, iters, ctypes.byref(ms), ctypes.byref(units)) != 0:
+                raise SystemExit("bench.py: probe %d failed" % which)
+        return units.value / (ms.value * 1e-3), ms.value
+
+    cus = L.adapt_probe_cu_count()
+    g16, _ = rate(0, 4000)
+    g16g, _ = rate(1, 4000)
+    b128, _ = rate(2, 1000)
+    dma, _ = rate(3, 720)
+    mfma, _ = rate(4, 2000)
+    _, ms5 = rate(5, 720)
+    return dict(cus=cus,
+                lds_gather16_conflict_free_Tlookup_s=g16 / 1e12,
+                lds_gather16_gaussian_row_Tlookup_s=g16g / 1e12,
+                lds_read_b128_TB_s=b128 / 1e12,
+                l2_to_lds_TB_s=dma / 1e12,
+                mfma_i32_16x16x64_i8_Ginst_s=mfma / 1e9,
+                quad_step_all_three_us=ms5 * 1e3 / 720,
+                how="probe kernels run by this script before the timed region (16 waves per compute unit; best of 3 launches each)")
 
 
 def _f(x):
@@ -311,6 +364,33 @@ def cpu_baseline(cfg_id, bits, wl):
     return dict(value=104628224 * 32 / dt, unit="LUT-MAC/s", cores=th, kind="oracle", sample="32 of 256 latent vectors, one pass incl. calibration")
 
 
+def network_roofline(cfg_id, bits, macs, ms_per_step, ceilings, model_peak, gnet):
+    """A whole network step priced against the measured ceilings: the time its lookups need at the rate of the resource
+    that bounds the kernel they run on (16-byte LDS reads for the derived-table kernels: 2 bytes per lookup; 16-bit LDS
+    gathers for the whole-table kernel: one per lookup), divided by the measured step time."""
+    if not ceilings or cfg_id not in (3, 4, 5, 6, 7):
+        return None
+    lds = ceilings["lds_read_b128_TB_s"] * 1e12
+    g16 = ceilings["lds_gather16_conflict_free_Tlookup_s"] * 1e12
+    if cfg_id == 4:
+        rec = 100 * 64 * 512 * 2048          # hidden-state products: one launch per time step on the whole-table kernel
+        proj = macs - rec                    # input products of all steps: one launch of the quad kernel
+        t = rec / g16 + 2.0 * proj / lds
+        dom, bound = "lut_rows_kernel (recurrent step: product + cell, 100 launches)", "lds_gather16 (recurrence) + lds_read (input products)"
+    elif cfg_id == 7:
+        rec = 100 * 64 * 512 * 1536
+        t = rec / g16 + 2.0 * (macs - rec) / lds
+        dom, bound = "lut_rows_kernel (recurrent step: product + cell, 100 launches)", "lds_gather16 (recurrence) + lds_read (input products)"
+    else:
+        t = 2.0 * macs / lds
+        dom = {3: "lut_lines_fast_kernel (128-byte lines; 19 launches of 18 - 30 us)", 5: "lut_quad_kernel<%d, 8, true>" % (4 if bits == 8 else 1),
+               6: "lut_grouped_tiled_kernel + lut_quad_kernel"}[cfg_id]
+        bound = "lds_read"
+    return dict(bound=bound, achieved=macs / (ms_per_step * 1e-3) / 1e12, peak=macs / t / 1e12, unit="Tlookup/s", frac=t / (ms_per_step * 1e-3),
+                traffic=None, bound_us=t * 1e6, dominant_kernel=dom, covers="the whole network step (every kernel, launch gaps included)",
+                peak_source="what the step's lookups cost at the LDS rates measured by the probe kernels in this run", ceilings=ceilings)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -322,6 +402,9 @@ def main():
                     "(rows beyond the baseline, not bench lines of record)")
     ap.add_argument("--bits", type=int, default=8, help="table bits for config 5 (6 or 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probes", action="store_true", help="skip the ceiling probes (roofline then falls back to model figures or is omitted)")
+    ap.add_argument("--no-others", action="store_true", help="default run: do not time the other baseline configurations after the headline one")
+    ap.add_argument("--other-steps", type=int, default=20, help="timed steps for each of the other configurations of the default run")
     ap.add_argument("--prewarm-ms", type=float, default=300.0,
                     help="untimed steps for this long before the warm-up steps, so that the device clocks have settled (0: none)")
     ap.add_argument("--eager", action="store_true", help="network configurations: launch kernel by kernel instead of replaying a HIP graph")
@@ -348,30 +431,47 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes": 64 << 20, "copies": 3}))
         return
+    # ceilings of this device, measured now (headline and network configurations price their kernels against them)
+    ceilings = run_probes() if args.config <= 7 and not args.no_probes else None
     step, core, macs, name, _keep = build_step(args.config, args.bits, torch, B, gnet, wl, args.eager)
 
-    # bring the device to its running clocks before anything is measured (a cold GPU runs the first tens of
-    # milliseconds slower; the W warm-up steps of the small configurations are over in well under a millisecond)
-    t_pre = time.perf_counter()
-    while time.perf_counter() - t_pre < args.prewarm_ms * 1e-3:
-        for _ in range(20):
-            step()
+    def timed(step_fn, steps, warmup, prewarm_ms):
+        # bring the device to its running clocks before anything is measured (a cold GPU runs the first tens of
+        # milliseconds slower; the W warm-up steps of the small configurations are over in well under a millisecond)
+        t_pre = time.perf_counter()
+        while time.perf_counter() - t_pre < prewarm_ms * 1e-3:
+            for _ in range(20):
+                step_fn()
+            torch.cuda.synchronize()
+        for _ in range(warmup):
+            step_fn()
         torch.cuda.synchronize()
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt * 1e3 / args.steps
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step_fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    ms_per_step = timed(step, args.steps, args.warmup, args.prewarm_ms)
 
     # dominant kernel: HIP events on the launch stream around the table-lookup call
     roof = None
     cus = B.adapt_device_cu_count()
-    traffic = args.traffic_bytes if args.traffic_bytes is not None else MEASURED_TRAFFIC_BYTES.get(args.config)
-    peak = cus * LDS_LANES_PER_CLK_PER_CU * MODEL_CLOCK_GHZ * 1e9
+    model_peak = cus * LDS_LANES_PER_CLK_PER_CU * MODEL_CLOCK_GHZ * 1e9
+    traffic_by_kernel = read_traffic()
+    traffic = args.traffic_bytes
+
+    def lookup_context(rate):
+        """The figure BASELINE names: lookups per second against one 2-byte lookup per bank-lane and clock."""
+        d = dict(achieved_Tlookup_s=rate / 1e12, model_peak_Tlookup_s=model_peak / 1e12, frac_of_model=rate / model_peak,
+                 model=f"{cus} CUs x {LDS_LANES_PER_CLK_PER_CU} LDS bank-lanes/clk x {MODEL_CLOCK_GHZ} GHz; 1 lookup (2 B) per LUT-MAC")
+        if ceilings:
+            g = ceilings["lds_gather16_conflict_free_Tlookup_s"] * 1e12
+            d.update(measured_conflict_free_gather_Tlookup_s=g / 1e12, frac_of_measured_gather=rate / g,
+                     note="a kernel on derived tables reads 16 bytes (8 entries) per LDS lane-access, so these two fractions are not "
+                          "bounded by 1 for it; its ceilings are the resources in roofline.resource_us")
+        return d
+
     if core is not None:
         # back-to-back launches between one pair of events per block, so the queue stays full and the figure is the
         # device time of the call's kernels, comparable with a kernel trace
@@ -389,54 +489,91 @@ def main():
 
         call_ms = event_ms(core)
         kernel_only = getattr(core, "kernel_only", None)
-        if kernel_only is not None:
-            # the dominant kernel by itself (launched on an input copy made beforehand): the duration a kernel trace
-            # lists for it; the call's other kernel (quantise + copy) is in call_ms_avg
-            kms = event_ms(kernel_only)
-            covers = "the product kernel alone (lut_lines_wide_kernel); call_ms_avg adds the call's quantise-and-copy kernel"
-            if args.traffic_bytes is None:
-                traffic = MEASURED_KERNEL_TRAFFIC_BYTES.get(args.config)
-            # second bound of the same kernel: the pipe that widens and adds the entries.  With a table whose range fits
-            # the digit form (this one does) that is the matrix pipe: two v_mfma_i32_16x16x64_i8 of 16 clocks per 512
-            # lookups of a wave, four SIMDs per compute unit
-            pipe_peak = cus * 4 * 512 / (2 * MFMA_16X16X64_CLOCKS) * MODEL_CLOCK_GHZ * 1e9
-            extra_bound = dict(pipe_bound="mfma (int8)", pipe_peak=pipe_peak / 1e12,
-                               pipe_frac=macs / (float(kms.mean()) * 1e-3) / pipe_peak,
-                               pipe_model=f"{cus} CUs x 4 SIMDs x 512 lookups per 2 v_mfma_i32_16x16x64_i8 of "
-                                          f"{MFMA_16X16X64_CLOCKS} clocks x {MODEL_CLOCK_GHZ} GHz")
-        else:
-            kms = call_ms
-            covers = "every kernel of the table-lookup call"
-            extra_bound = {}
+        kms = event_ms(kernel_only) if kernel_only is not None else call_ms
         k_avg = float(kms.mean())
         achieved = macs / (k_avg * 1e-3)
-        roof = dict(bound="lds", achieved=achieved / 1e12, peak=peak / 1e12, unit="Tlookup/s", frac=achieved / peak,
-                    traffic=traffic, kernel_ms_avg=k_avg, kernel_ms_min=float(kms.min()),
-                    call_ms_avg=float(call_ms.mean()), call_frac=macs / (float(call_ms.mean()) * 1e-3) / peak,
-                    call_traffic=MEASURED_TRAFFIC_BYTES.get(args.config), covers=covers, **extra_bound,
-                    peak_model=f"{cus} CUs x {LDS_LANES_PER_CLK_PER_CU} LDS bank-lanes/clk x {MODEL_CLOCK_GHZ} GHz; "
-                               "1 lookup (2 B) per LUT-MAC")
-        if args.config == 8:
-            # a table beyond LDS is gathered through the vector memory path: 4 lane addresses per clock per compute unit
-            gpeak = cus * GATHER_LANES_PER_CLK_PER_CU * MODEL_CLOCK_GHZ * 1e9
-            roof.update(bound="l1-gather", peak=gpeak / 1e12, frac=achieved / gpeak,
-                        peak_model=f"{cus} CUs x {GATHER_LANES_PER_CLK_PER_CU} gathered lanes/clk x {MODEL_CLOCK_GHZ} GHz; "
-                                   "1 lookup (4 B from device memory) per LUT-MAC")
-        if args.config in (10, 11):
+        if args.config == 2 and ceilings:
+            # The product kernel of the headline layer (lut_quad_kernel), priced resource by resource: what one launch
+            # needs of each, divided by what the probes measured for it a moment ago.  The largest of these times is the
+            # bound; frac = that time / the kernel's measured time.
+            kern, rpw, ksplit, steps_k, wgs = B.adapt_plan_packed(1, 8, 0, 64, 64, 3, 3, 1, 32768, 32, 1)
+            if kern != 3:
+                raise SystemExit("bench.py: the headline layer is not planned on the quad kernel")
+            table_bytes = 256 << 8
+            lds_bytes = 2.0 * macs                                          # one 16-byte read per 8 lookups
+            fill_bytes = float(wgs) * (steps_k / ksplit) * (table_bytes + rpw * 16)  # tables into LDS + activations into registers, per step
+            mfma_insts = macs / 512.0                                       # one matrix instruction per 64 reads
+            hbm_bytes = 32 * 34 * 34 * 64 + 8 * steps_k * table_bytes + 4.0 * 32 * 64 * 32 * 32      # padded copy + tables + fp32 output
+            res_us = dict(lds_read=lds_bytes / (ceilings["lds_read_b128_TB_s"] * 1e12) * 1e6,
+                          l2_to_cu_fill=fill_bytes / (ceilings["l2_to_lds_TB_s"] * 1e12) * 1e6,
+                          mfma=mfma_insts / (ceilings["mfma_i32_16x16x64_i8_Ginst_s"] * 1e9) * 1e6,
+                          hbm=hbm_bytes / HBM_PEAK_BYTES_PER_S * 1e6)
+            bound = max(res_us, key=res_us.get)
+            amount, peak_v, unit = {"lds_read": (lds_bytes, ceilings["lds_read_b128_TB_s"], "TB/s"),
+                                    "l2_to_cu_fill": (fill_bytes, ceilings["l2_to_lds_TB_s"], "TB/s"),
+                                    "mfma": (mfma_insts * 32768, ceilings["mfma_i32_16x16x64_i8_Ginst_s"] * 1e9 * 32768 / 1e12, "TOP/s"),
+                                    "hbm": (hbm_bytes, HBM_PEAK_BYTES_PER_S / 1e12, "TB/s")}[bound]
+            if traffic is None:
+                traffic = traffic_by_kernel.get("lut_quad_kernel")
+            roof = dict(bound=bound, achieved=amount / (k_avg * 1e-3) / 1e12, peak=peak_v, unit=unit, frac=res_us[bound] / (k_avg * 1e3),
+                        traffic=traffic, traffic_source=os.path.relpath(TRAFFIC_FILE, ROOT) if traffic is not None and args.traffic_bytes is None else None,
+                        kernel="lut_quad_kernel<4, %d, false>" % (rpw // 256), kernel_ms_avg=k_avg, kernel_ms_min=float(kms.min()),
+                        call_ms_avg=float(call_ms.mean()), call_traffic=(traffic + traffic_by_kernel["pad_channels_last"]) if traffic is not None and "pad_channels_last" in traffic_by_kernel else None,
+                        covers="the product kernel alone, launched on an input copy made beforehand; call_ms_avg adds the call's quantise-and-copy kernel",
+                        resource_us=res_us, algorithmic=dict(lds_bytes=lds_bytes, l2_to_cu_fill_bytes=fill_bytes, mfma_instructions=mfma_insts, hbm_bytes=hbm_bytes,
+                                                             workgroups=wgs, steps=steps_k, rows_per_workgroup=rpw),
+                        all_three_together_us=ceilings["quad_step_all_three_us"] * steps_k / ksplit * ((wgs + cus - 1) // cus),
+                        peak_source="measured by the probe kernels in this run (roofline.ceilings)", ceilings=ceilings,
+                        lookups=lookup_context(achieved))
+        elif args.config in (10, 11):
             # two dense fp32 contractions (macs counts the multiply-adds of both): the matrix pipe's fp32 rate
             roof = dict(bound="mfma", achieved=2 * achieved / 1e12, peak=157.3, unit="TFLOP/s", frac=2 * achieved / 157.3e12, traffic=None,
                         kernel_ms_avg=k_avg, kernel_ms_min=float(kms.min()), covers="every kernel of the call (products, bias gradient; convolution: also the unfolding and gathering kernels)",
                         peak_model="published dense fp32 matrix rate of MI355X")
-        if args.config == 9:
+        elif args.config == 8:
+            # a table beyond LDS is gathered through the vector memory path: 4 lane addresses per clock per compute unit
+            gpeak = cus * GATHER_LANES_PER_CLK_PER_CU * MODEL_CLOCK_GHZ * 1e9
+            roof = dict(bound="l1-gather", achieved=achieved / 1e12, peak=gpeak / 1e12, unit="Tlookup/s", frac=achieved / gpeak, traffic=traffic,
+                        kernel_ms_avg=k_avg, kernel_ms_min=float(kms.min()),
+                        peak_model=f"{cus} CUs x {GATHER_LANES_PER_CLK_PER_CU} gathered lanes/clk x {MODEL_CLOCK_GHZ} GHz; 1 lookup (4 B from device memory) per LUT-MAC")
+        elif args.config == 9:
             # the multiplier as a function: vector integer operations, 64 lanes per clock per compute unit
             apeak = cus * 64 * MODEL_CLOCK_GHZ * 1e9 / MITCHELL_OPS_PER_MAC
-            roof.update(bound="alu", peak=apeak / 1e12, unit="TMAC/s", frac=achieved / apeak,
-                        peak_model=f"{cus} CUs x 64 lanes/clk x {MODEL_CLOCK_GHZ} GHz / {MITCHELL_OPS_PER_MAC} vector "
-                                   "instructions per Mitchell multiply-accumulate")
+            roof = dict(bound="alu", achieved=achieved / 1e12, peak=apeak / 1e12, unit="TMAC/s", frac=achieved / apeak, traffic=traffic,
+                        kernel_ms_avg=k_avg, kernel_ms_min=float(kms.min()),
+                        peak_model=f"{cus} CUs x 64 lanes/clk x {MODEL_CLOCK_GHZ} GHz / {MITCHELL_OPS_PER_MAC} vector instructions per Mitchell multiply-accumulate")
+        else:
+            # whole-table kernel (configuration 1 and other short products): one 16-bit LDS gather per lookup
+            g = (ceilings["lds_gather16_conflict_free_Tlookup_s"] * 1e12) if ceilings else model_peak
+            roof = dict(bound="lds_gather16", achieved=achieved / 1e12, peak=g / 1e12, unit="Tlookup/s", frac=achieved / g, traffic=traffic,
+                        kernel_ms_avg=k_avg, kernel_ms_min=float(kms.min()), covers="every kernel of the table-lookup call",
+                        peak_source="conflict-free 16-bit LDS gathers measured by the probe kernel in this run" if ceilings else "model",
+                        ceilings=ceilings, lookups=lookup_context(achieved))
     else:
-        achieved = macs / (ms_per_step * 1e-3)
-        roof = dict(bound="lds", achieved=achieved / 1e12, peak=peak / 1e12, unit="Tlookup/s", frac=achieved / peak,
-                    traffic=traffic, note="whole network step (all kernels) against the LDS lookup peak")
+        roof = network_roofline(args.config, args.bits, macs, ms_per_step, ceilings, model_peak, gnet)
+        if roof is not None:
+            roof["lookups"] = lookup_context(macs / (ms_per_step * 1e-3))
+
+    # the other baseline configurations, after the headline measurement (default run only)
+    others = None
+    if args.config == 2 and not args.no_others:
+        others = []
+        del step, core, _keep
+        torch.cuda.empty_cache()
+        for cfg, bits in ((1, 8), (3, 8), (4, 7), (5, 6), (5, 8)):
+            st, co, m, nm, keep = build_step(cfg, bits, torch, B, gnet, wl, False)
+            ms = timed(st, args.other_steps, 3, 100.0)
+            entry = dict(workload=nm, lut_macs_per_step=m, steps=args.other_steps, ms_per_step=ms, value=m / (ms * 1e-3), unit="LUT-MAC/s")
+            if co is not None:
+                g = ceilings["lds_gather16_conflict_free_Tlookup_s"] * 1e12 if ceilings else model_peak
+                entry.update(dominant_kernel="lut_rows_kernel (whole table in LDS)", bound="lds_gather16", frac=m / (ms * 1e-3) / g)
+            else:
+                r = network_roofline(cfg, bits, m, ms, ceilings, model_peak, gnet)
+                if r:
+                    entry.update(dominant_kernel=r["dominant_kernel"], bound=r["bound"], frac=r["frac"], bound_us=r["bound_us"])
+            others.append(entry)
+            del st, co, keep
+            torch.cuda.empty_cache()
 
     out = {
         "metric": ("approximate MACs/sec (LUT-MAC/s), whole step: quantise + table-lookup layer(s) + dequantise" if args.config not in (10, 11) else
@@ -452,6 +589,8 @@ def main():
         "config": {"workload": name, ("lut_macs_per_step" if args.config not in (10, 11) else "multiply_adds_per_step"): macs},
         "roofline": roof,
     }
+    if others is not None:
+        out["others"] = others
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, args.bits, wl)
     print(json.dumps(out))

@@ -348,92 +348,90 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
     asm volatile("s_nop 15\n\ts_nop 15" : : : "memory");
 #pragma unroll
     for (int i = 0; i < R; ++i) asm volatile("" : "+v"(acc[i]));
-    // lanes l and l ^ 32 hold the two parts (rows ch and 8 + ch of D) of the same sums
-    uint32_t sum[R][4];
+    // Lanes l and l ^ 32 hold the two parts (rows ch and 8 + ch of D) of the sums of channels 4 (q % 2) .. + 3 of the row
+    // slot's R pixels.  Lane q < 2 finishes the first two of these channels, lane q >= 2 the other two, each for all R
+    // pixels: every lane hands its partner the parts the partner will finish and adds what it is handed.  A lane then
+    // stores runs of four consecutive pixels (16 bytes) and the 16 lanes of a k-sub a whole 256-byte stretch of one
+    // channel in one instruction.
+    constexpr int NRUN = R / 4;             // runs of four pixels
+    const int hi = q >> 1;
+    const int cb = nt * 8 + 4 * (q & 1);    // first channel of the quad that the two lanes share
+    uint32_t w[R][2];
 #pragma unroll
     for (int i = 0; i < R; ++i) {
         const int part[4] = {acc[i].x, acc[i].y, acc[i].z, acc[i].w};
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-            sum[i][c] = (uint32_t)part[c] + (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, part[c]);
+        for (int cc = 0; cc < 2; ++cc) {
+            const int keep = hi ? part[2 + cc] : part[cc], give = hi ? part[cc] : part[2 + cc];
+            w[i][cc] = (uint32_t)keep + (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, give);
+            if (ks == 0) w[i][cc] += (uint32_t)p.corr;      // the offset of the digit form, once per output
+        }
     }
-    // Both lanes now hold channels 4 (q % 2) .. + 3 of the row slot's R pixels; lane q < 2 finishes the first half of
-    // the pixels, lane q >= 2 the second.
-    constexpr int NP = R / 2;               // pixels per lane in the epilogue
-    const int half = q >> 1;
-    const int cb = nt * 8 + 4 * (q & 1);    // first of this lane's four channels
-    uint32_t w[NP][4];
-#pragma unroll
-    for (int i = 0; i < NP; ++i)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) w[i][c] = half ? sum[NP + i][c] : sum[i][c];
     if (!live) return;                      // no barrier follows
-    if (ks == 0) {                          // the offset of the digit form, once per output
-#pragma unroll
-        for (int i = 0; i < NP; ++i)
-#pragma unroll
-            for (int c = 0; c < 4; ++c) w[i][c] += (uint32_t)p.corr;
-    }
-    int img, a0, b0;
-    row_pos(r0 + NP * half, img, a0, b0);   // (a lane's NP pixels lie in one image row: Wo is a multiple of 4)
-    // transposed convolution (EXTRA instantiation, zsum given): the phase's output pixels are (oy, ox + i * out_sx); the
-    // taps that lay over the zero border are taken off for the few pixels that touch the border
-    int oy = 0, ox = 0;
-    bool near_border = false;
     const bool true_pos = EXTRA && p.cv_Wo > 0 && (p.zsum || p.chain.buf);      // (cv_Wo > 0: a transposed convolution)
-    if (true_pos) {
-        const int oy0 = out_off / p.cv_Wo, ox0 = out_off - oy0 * p.cv_Wo;       // uniform: once per workgroup
-        oy = oy0 + a0 * (p.out_sy / p.cv_Wo);
-        ox = ox0 + b0 * p.out_sx;
-        if (p.zsum) near_border = oy < p.cv_Ly || oy >= p.cv_Ho - p.cv_Ly || ox < p.cv_Lx || ox + (NP - 1) * p.out_sx >= p.cv_Wo - p.cv_Lx;
-    }
     const int sx = p.out_sx;
-    uint32_t codes[NP];
-#pragma unroll
-    for (int i = 0; i < NP; ++i) codes[i] = 0u;
     const bool quad_ok = cb + 3 < p.N;      // the whole channel quad exists: a chained copy takes it as one word per pixel
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const int n = cb + c;
-        if (n >= p.N) continue;
-        if (EXTRA && near_border) {
-#pragma unroll
-            for (int i = 0; i < NP; ++i) w[i][c] -= convt_border_terms(p, n, oy, ox + i * p.out_sx);
+    for (int run = 0; run < NRUN; ++run) {
+        int img, a0, b0;
+        row_pos(r0 + 4 * run, img, a0, b0); // (a run lies in one image row: Wo is a multiple of 4)
+        // transposed convolution (EXTRA instantiation, zsum given): the phase's output pixels are (oy, ox + i * out_sx);
+        // the taps that lay over the zero border are taken off for the few runs that touch the border
+        int oy = 0, ox = 0;
+        bool near_border = false;
+        if (true_pos) {
+            const int oy0 = out_off / p.cv_Wo, ox0 = out_off - oy0 * p.cv_Wo;   // uniform: once per workgroup
+            oy = oy0 + a0 * (p.out_sy / p.cv_Wo);
+            ox = ox0 + b0 * p.out_sx;
+            if (p.zsum) near_border = oy < p.cv_Ly || oy >= p.cv_Ho - p.cv_Ly || ox < p.cv_Lx || ox + 3 * p.out_sx >= p.cv_Wo - p.cv_Lx;
         }
-        int32_t *q0 = outp + ((size_t)img * p.N + n) * p.out_plane + out_off + a0 * p.out_sy + b0 * p.out_sx;
-        uint32_t f[NP];
+        uint32_t pk[4] = {0u, 0u, 0u, 0u};  // chained copy: this lane's two codes per pixel (byte cc = channel 2 hi + cc)
 #pragma unroll
-        for (int i = 0; i < NP; ++i) f[i] = finish_sum<EXTRA>(p, w[i][c], n, (size_t)(q0 + i * sx - outp));
-        if (EXTRA && p.chain.buf) {
+        for (int cc = 0; cc < 2; ++cc) {
+            const int n = cb + 2 * hi + cc;
+            if (n >= p.N) continue;
+            uint32_t v[4];
 #pragma unroll
-            for (int i = 0; i < NP; ++i) {
-                if (quad_ok) codes[i] |= p.chain.code(__uint_as_float(f[i])) << (8 * c);
-                else if (true_pos) p.chain.put(img, n, oy, ox + i * p.out_sx, __uint_as_float(f[i]));
-                else p.chain.put(img, n, a0, b0 + i, __uint_as_float(f[i]));
+            for (int i = 0; i < 4; ++i) v[i] = w[4 * run + i][cc];
+            if (EXTRA && near_border) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] -= convt_border_terms(p, n, oy, ox + i * p.out_sx);
             }
-        }
-        bool stored = false;
-        if constexpr (NP == 4) {
+            int32_t *q0 = outp + ((size_t)img * p.N + n) * p.out_plane + out_off + a0 * p.out_sy + b0 * p.out_sx;
+            uint32_t f[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) f[i] = finish_sum<EXTRA>(p, v[i], n, (size_t)(q0 + i * sx - outp));
+            if (EXTRA && p.chain.buf) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (quad_ok) pk[i] |= p.chain.code(__uint_as_float(f[i])) << (8 * cc);
+                    else if (true_pos) p.chain.put(img, n, oy, ox + i * p.out_sx, __uint_as_float(f[i]));
+                    else p.chain.put(img, n, a0, b0 + i, __uint_as_float(f[i]));
+                }
+            }
             if (sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
                 *reinterpret_cast<uint4 *>(q0) = make_uint4(f[0], f[1], f[2], f[3]);
-                stored = true;
-            }
-        } else if constexpr (NP == 2) {
-            if (sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 7u) == 0) {
-                *reinterpret_cast<uint2 *>(q0) = make_uint2(f[0], f[1]);
-                stored = true;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) q0[i * sx] = (int32_t)f[i];
             }
         }
-        if (!stored) {
+        if (EXTRA && p.chain.buf) {
+            // The two lanes hold the two halves of every pixel's channel quad.  Each hands the other the pixels it will
+            // not write (lane hi = 0 writes pixels 0 and 1, lane hi = 1 pixels 2 and 3) and stores whole words.  Both
+            // lanes of a pair are live together, so the exchange is uniform.
+            const uint32_t give = hi ? (pk[0] | (pk[1] << 16)) : (pk[2] | (pk[3] << 16));
+            const uint32_t got = (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, (int)give);
+            if (quad_ok) {
 #pragma unroll
-            for (int i = 0; i < NP; ++i) q0[i * sx] = (int32_t)f[i];
-        }
-    }
-    if (EXTRA && p.chain.buf && quad_ok) {
-#pragma unroll
-        for (int i = 0; i < NP; ++i) {
-            if (true_pos) p.chain.put4(img, cb, oy, ox + i * p.out_sx, codes[i]);
-            else p.chain.put4(img, cb, a0, b0 + i, codes[i]);
+                for (int i = 0; i < 2; ++i) {
+                    const uint32_t theirs = (got >> (16 * i)) & 0xffffu, mine = pk[2 * hi + i];
+                    const uint32_t word = hi ? (theirs | (mine << 16)) : (mine | (theirs << 16));
+                    const int px = 2 * hi + i;
+                    if (true_pos) p.chain.put4(img, cb, oy, ox + px * p.out_sx, word);
+                    else p.chain.put4(img, cb, a0, b0 + px, word);
+                }
+            }
         }
     }
 }
