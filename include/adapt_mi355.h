@@ -32,6 +32,11 @@
  *     overlap in time; once a handle has run at its largest input size its calls
  *     allocate nothing and may be recorded into a HIP graph (which a later call
  *     at a larger size, re-allocating the workspace, would invalidate).
+ *   - Environment variables the library reads (debugging and measurement aids; results never depend on them):
+ *     ADAPT_POISON_ALLOC   any value: every device allocation the library makes is filled with 0xA5 bytes before
+ *                          use, so that code relying on fresh memory being zero shows up in tests.
+ *     ADAPT_STE_TILE       64 or 128: forces the output tile of the gradient products of adapt_ste_*_backward_f32
+ *     ADAPT_STE_KS         1 or 2: forces four or eight waves per workgroup there (both normally chosen from the shape).
  */
 #ifndef ADAPT_MI355_H
 #define ADAPT_MI355_H

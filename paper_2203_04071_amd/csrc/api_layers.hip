@@ -646,7 +646,7 @@ int launch_pad(const LayerIO *io, const int8_t *x, int bits, int8_t *xt, int N, 
     if (!blocks) return ADAPT_OK;
     const adapt::FastDiv dwp = fast_div((uint32_t)(W + 2 * pw)), dc4 = fast_div((uint32_t)(Cp / 4)), dhp = fast_div((uint32_t)(H + 2 * ph));
     const int fast = total < 0x7fffffffull ? 1 : 0;
-    if (fast && (size_t)N * C * H * W < 0x7fffffffull && total * 4 < 0x7fffffffull && !getenv("ADAPT_PAD_SINGLE")) {
+    if (fast && (size_t)N * C * H * W < 0x7fffffffull && total * 4 < 0x7fffffffull) {
         // several words per thread, all operands in flight together
         constexpr int U = 2;
         const unsigned mblocks = (unsigned)(((total + U - 1) / U + 255) / 256);

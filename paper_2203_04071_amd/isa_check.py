@@ -51,10 +51,11 @@ def _functions(txt, pattern):
         if name is None:
             continue
         s = line.strip()
-        body.append((ln, s))
-        if s.startswith('s_endpgm'):
+        if s.startswith('.Lfunc_end'):          # (blocks may follow an s_endpgm: the function ends at its end label)
             yield name, body
             name, body = None, []
+            continue
+        body.append((ln, s))
     if name:
         yield name, body
 

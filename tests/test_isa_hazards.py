@@ -35,3 +35,50 @@ def test_checker_flags_a_planted_copy(tmp_path):
     assert isa_check.check(str(p), "kernel") == 0
     p.write_text(bad)
     assert isa_check.check(str(p), "kernel") == 1
+
+
+def test_checker_flags_a_touched_matrix_accumulator(tmp_path):
+    """A compiler-generated instruction that reads the destination of a matrix instruction issued from asm, before the
+    kernel has drained the matrix pipe, must be reported; after the drain it is fine."""
+    good = """_Z6kernelv:
+\t;;#ASMSTART
+\tv_mfma_i32_16x16x64_i8 v[4:7], v[8:11], v[12:15], v[4:7]
+\t;;#ASMEND
+\tv_mov_b32_e32 v20, v8
+\t;;#ASMSTART
+\ts_nop 15
+\ts_nop 15
+\t;;#ASMEND
+\tv_mov_b32_e32 v21, v5
+\ts_endpgm
+"""
+    bad = good.replace("v_mov_b32_e32 v20, v8", "v_mov_b32_e32 v20, v6")
+    p = tmp_path / "k.s"
+    p.write_text(good)
+    assert isa_check.check(str(p), "kernel") == 0
+    p.write_text(bad)
+    assert isa_check.check(str(p), "kernel") == 1
+
+
+def test_checker_follows_branches(tmp_path):
+    """The walk follows the control-flow graph: a load issued in a block that the text puts AFTER its consumer is still
+    seen in flight when a branch leads from one to the other."""
+    text = """_Z6kernelv:
+\ts_branch .LBB0_2
+.LBB0_1:
+\tv_mov_b32_e32 v9, v5
+\t;;#ASMSTART
+\ts_waitcnt vmcnt(0)
+\t;;#ASMEND
+\ts_endpgm
+.LBB0_2:
+\t;;#ASMSTART
+\tglobal_load_dwordx4 v[4:7], v1, s[2:3]
+\t;;#ASMEND
+\ts_branch .LBB0_1
+"""
+    p = tmp_path / "k.s"
+    p.write_text(text)
+    assert isa_check.check(str(p), "kernel") == 1
+    p.write_text(text.replace("v_mov_b32_e32 v9, v5", "v_mov_b32_e32 v9, v3"))
+    assert isa_check.check(str(p), "kernel") == 0
