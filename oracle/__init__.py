@@ -225,6 +225,16 @@ def mse_from_histogram(counts, amax, bits) -> np.float32:
     return np.float32(out.value)
 
 
+def entropy_from_histogram(counts, amax, bits, with_losses=False):
+    """calib_max by smallest Kullback-Leibler loss (see orc_entropy_from_histogram); with_losses: also KL_k, k = 1 .. bins."""
+    counts = np.ascontiguousarray(counts, dtype=np.uint32)
+    out = ctypes.c_float(0.0)
+    kl = np.empty(counts.size, dtype=np.float64) if with_losses else None
+    _check(lib().orc_entropy_from_histogram(_p(counts), int(counts.size), ctypes.c_float(float(amax)), ctypes.c_int(bits),
+                                            ctypes.byref(out), _p(kl) if with_losses else None), "entropy_from_histogram")
+    return (np.float32(out.value), kl) if with_losses else np.float32(out.value)
+
+
 def relu(x) -> np.ndarray:
     x = _f32(x)
     y = np.empty_like(x)

@@ -378,6 +378,63 @@ int orc_mse_from_histogram(const uint32_t *counts, int bins, float amax, int bit
     return ORC_OK;
 }
 
+/* calib_max by smallest information loss ("entropy" calibrator: Sec. III-A names it as a third alternative without
+ * defining it; the definition below is this build's reading of the published idea - keep the range whose quantised
+ * histogram diverges least, in the Kullback-Leibler sense, from the histogram it stands for).
+ * L = 2^(bits-1) magnitude levels.  A candidate keeps the first k bins, k = L .. bins (k = bins alone when bins < L):
+ *   reference  p_j = counts[j] for j < k - 1,  p_{k-1} = counts[k-1] + everything beyond (saturated values land there);
+ *   quantised  the k kept bins WITHOUT that outlier mass are merged into L groups, group g = bins [g k / L, (g+1) k / L)
+ *              (integer divisions); a bin with counts[j] > 0 gets q_j = (sum of its group) / (non-empty bins of its group),
+ *              an empty bin q_j = 0;
+ *   loss       KL_k = sum over j < k with p_j > 0, ascending, of (p_j / P) log((p_j / P) / (q_j / Q)),  P = sum p, Q = sum q;
+ *              +inf when some p_j > 0 meets q_j = 0 (outliers pushed into an empty last bin).
+ * fp64 throughout, every operation rounded on its own.  The first k with the smallest loss wins: calib_max = k * width.
+ * kl (optional): KL_k for k = 1 .. bins at kl[k - 1] (+inf for k that are no candidates). */
+int orc_entropy_from_histogram(const uint32_t *counts, int bins, float amax, int bits, float *calib_max, double *kl) {
+    if (!counts || !calib_max || bins < 1 || !(amax > 0.0f) || bits < 2 || bits > 16) return ORC_BAD_ARG;
+    const float width = amax / (float)bins;
+    const long L = 1L << (bits - 1);
+    unsigned long long total = 0;
+    for (int j = 0; j < bins; ++j) total += counts[j];
+    if (kl) for (int k = 0; k < bins; ++k) kl[k] = INFINITY;
+    if (total == 0) { *calib_max = (float)bins * width; return ORC_OK; }
+    const double P = (double)total;
+    const int k_first = L < bins ? (int)L : bins;
+    double best = 0.0;
+    int best_k = -1;
+    unsigned long long kept = 0;                 /* counts[0 .. k-1] */
+    for (int j = 0; j < k_first - 1; ++j) kept += counts[j];
+    for (int k = k_first; k <= bins; ++k) {
+        kept += counts[k - 1];
+        const unsigned long long outliers = total - kept;
+        const long groups = L < k ? L : k;       /* (bins < L: one bin per group) */
+        double Q = 0.0;                          /* sum of q over the kept bins = kept, formed the way q is formed */
+        for (long g = 0; g < groups; ++g) {
+            const long lo = g * k / groups, hi = (g + 1) * k / groups;
+            unsigned long long sg = 0; long zg = 0;
+            for (long j = lo; j < hi; ++j) { sg += counts[j]; zg += counts[j] > 0; }
+            if (zg) Q = Q + (double)zg * ((double)sg / (double)zg);
+        }
+        double loss = 0.0;
+        for (long g = 0; g < groups; ++g) {
+            const long lo = g * k / groups, hi = (g + 1) * k / groups;
+            unsigned long long sg = 0; long zg = 0;
+            for (long j = lo; j < hi; ++j) { sg += counts[j]; zg += counts[j] > 0; }
+            for (long j = lo; j < hi; ++j) {
+                const unsigned long long pj = (unsigned long long)counts[j] + (j == k - 1 ? outliers : 0ULL);
+                if (!pj) continue;
+                if (!counts[j]) { loss = INFINITY; continue; }
+                const double pn = (double)pj / P, qn = ((double)sg / (double)zg) / Q;
+                loss = loss + pn * log(pn / qn);
+            }
+        }
+        if (kl) kl[k - 1] = loss;
+        if (best_k < 0 || loss < best) { best = loss; best_k = k; }
+    }
+    *calib_max = (float)best_k * width;
+    return ORC_OK;
+}
+
 /* ---------------------------------------------------------------------------
  * fp32 glue between approximate layers.  Each is one IEEE operation per element
  * in the stated order, so that the integers produced by the next quantiser are

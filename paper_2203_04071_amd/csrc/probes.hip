@@ -8,6 +8,11 @@
 //   3  L2 -> LDS copies of 64 KB tables by LDS-direct loads, one table stream per XCD-resident group of workgroups
 //   4  v_mfma_i32_16x16x64_i8 on independent accumulators
 //   5  2, 3 and 4 together in the proportions of one quad-kernel step (4 rows per row slot), with its barrier
+//   6  16-bit LDS gathers inside one 256-byte row of a 7-bit table, uniform activations (the recurrent time step)
+//   7  the same with two copies of the table, the second rotated by 16 banks, even lanes on one and odd lanes on the other
+//   8  8-bit LDS gathers inside one 128-byte row (a 7-bit table of one-byte entries: one word per bank)
+//   9  the row held in a register across the wave and gathered with ds_bpermute_b32: per lookup one conflict-free
+//      ds_read_b32 (the row) + one ds_bpermute_b32 (the gather)
 // extern "C" adapt_probe_run(which, iters, &ms, &units): runs probe `which` on the current device (default stream,
 // synchronous, best of three launches), returns the kernel time in ms and the units one launch processed (lookups for 0
 // and 1, bytes for 2 and 3, matrix instructions for 4, steps x workgroups for 5).  Returns 0, or -1 on a HIP error.
@@ -36,7 +41,15 @@ __global__ __launch_bounds__(THREADS) void lds_read_probe(const uint32_t *__rest
     for (int j = 0; j < 8; ++j) a[j] = base + addrs[(size_t)j * THREADS + threadIdx.x];
     uint32_t acc = 0;
     for (int it = 0; it < iters; ++it) {
-        if (WIDTH == 2) {
+        if (WIDTH == 1) {
+            uint32_t r0, r1, r2, r3, r4, r5, r6, r7;
+            asm volatile("ds_read_i8 %0, %8\n ds_read_i8 %1, %9\n ds_read_i8 %2, %10\n ds_read_i8 %3, %11\n"
+                         "ds_read_i8 %4, %12\n ds_read_i8 %5, %13\n ds_read_i8 %6, %14\n ds_read_i8 %7, %15\n"
+                         "s_waitcnt lgkmcnt(0)\n"
+                         : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3), "=&v"(r4), "=&v"(r5), "=&v"(r6), "=&v"(r7)
+                         : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]));
+            acc += r0 + r1 + r2 + r3 + r4 + r5 + r6 + r7;
+        } else if (WIDTH == 2) {
             uint32_t r0, r1, r2, r3, r4, r5, r6, r7;
             asm volatile("ds_read_u16 %0, %8\n ds_read_u16 %1, %9\n ds_read_u16 %2, %10\n ds_read_u16 %3, %11\n"
                          "ds_read_u16 %4, %12\n ds_read_u16 %5, %13\n ds_read_u16 %6, %14\n ds_read_u16 %7, %15\n"
@@ -53,6 +66,34 @@ __global__ __launch_bounds__(THREADS) void lds_read_probe(const uint32_t *__rest
                          : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]));
             const u32x4_t s = r0 + r1 + r2 + r3 + r4 + r5 + r6 + r7;
             acc += s.x + s.y + s.z + s.w;
+        }
+    }
+    out[(size_t)blockIdx.x * THREADS + threadIdx.x] = acc;
+}
+
+// Row in a register, gather by ds_bpermute_b32: per lookup the row of the (wave-uniform) weight is read with lane l
+// taking word l (conflict-free), then every lane fetches word (activation / 2) of it from the lane that holds it.
+__global__ __launch_bounds__(THREADS) void bpermute_probe(const uint32_t *__restrict__ addrs, int iters, uint32_t *out) {
+    __shared__ __attribute__((aligned(65536))) uint32_t smem[32768];
+    for (int i = threadIdx.x; i < 32768; i += THREADS) smem[i] = (uint32_t)i * 2654435761u;
+    __syncthreads();
+    const uint32_t base = (uint32_t)(uintptr_t)(lds_ptr)smem, lane = threadIdx.x & 63;
+    uint32_t rowaddr[8], sel[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t a = addrs[(size_t)j * THREADS + threadIdx.x];      // row * 256 + entry * 2
+        rowaddr[j] = base + (a & ~255u) + lane * 4;
+        sel[j] = ((a & 255u) >> 2) << 2;                                    // lane that holds the entry's word, times 4
+    }
+    uint32_t acc = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            uint32_t row, got;
+            asm volatile("ds_read_b32 %0, %2\n\ts_waitcnt lgkmcnt(0)\n\tds_bpermute_b32 %1, %3, %0\n\ts_waitcnt lgkmcnt(0)"
+                         : "=&v"(row), "=&v"(got)
+                         : "v"(rowaddr[j]), "v"(sel[j]));
+            acc += got;
         }
     }
     out[(size_t)blockIdx.x * THREADS + threadIdx.x] = acc;
@@ -160,11 +201,16 @@ std::vector<uint32_t> pattern(int which) {
                     int q = (int)std::lrint(gauss(rng));
                     q = q < -128 ? -128 : (q > 127 ? 127 : q);
                     v = row * 512 + (uint32_t)(q + 128) * 2;
-                } else v = (rng() % 16) * 256 + (uint32_t)(l % 16) * 16;                   // slot = lane % 16 of a random line (first 4 KB; + 4096 j' in the kernel)
+                } else if (which == 6 || which == 9) v = (row % 128) * 256 + (rng() % 128) * 2;      // 7-bit row, uniform entry
+                else if (which == 7) {                                                     // two copies, odd lanes on the rotated one
+                    const uint32_t e2 = (rng() % 128) * 2;
+                    v = (l & 1) ? 32768 + (row % 128) * 256 + ((e2 + 64) & 255) : (row % 128) * 256 + e2;
+                } else if (which == 8) v = (row % 128) * 128 + (rng() % 128);              // one-byte entries
+                else v = (rng() % 16) * 256 + (uint32_t)(l % 16) * 16;                   // slot = lane % 16 of a random line (first 4 KB; + 4096 j' in the kernel)
                 a[(size_t)j * THREADS + w * 64 + l] = v;
             }
         }
-    if (which >= 2)     // spread the lines over the whole 64 KB buffer: line = random
+    if (which >= 2 && which <= 5)     // spread the lines over the whole 64 KB buffer: line = random
         for (auto &v : a) v = (v & 0xff) | ((rng() % 240) << 8);
     return a;
 }
@@ -174,8 +220,8 @@ std::vector<uint32_t> pattern(int which) {
 extern "C" int adapt_probe_cu_count(void) { return setup() ? g.cus : -1; }
 
 extern "C" int adapt_probe_run(int which, int iters, float *ms_out, double *units_out) {
-    if (!setup() || which < 0 || which > 5 || iters < 1 || !ms_out || !units_out) return -1;
-    const std::vector<uint32_t> a = pattern(which < 2 ? which : 2);
+    if (!setup() || which < 0 || which > 9 || iters < 1 || !ms_out || !units_out) return -1;
+    const std::vector<uint32_t> a = pattern(which < 2 || which > 5 ? which : 2);
     if (hipMemcpy(g.addrs, a.data(), a.size() * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess) return -1;
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return -1;
@@ -185,7 +231,9 @@ extern "C" int adapt_probe_run(int which, int iters, float *ms_out, double *unit
     for (int rep = 0; rep < 3; ++rep) {
         (void)hipEventRecord(e0, nullptr);
         switch (which) {
-            case 0: case 1: lds_read_probe<2><<<grid, block>>>(g.addrs, iters, g.out); break;
+            case 0: case 1: case 6: case 7: lds_read_probe<2><<<grid, block>>>(g.addrs, iters, g.out); break;
+            case 8: lds_read_probe<1><<<grid, block>>>(g.addrs, iters, g.out); break;
+            case 9: bpermute_probe<<<grid, block>>>(g.addrs, iters, g.out); break;
             case 2: lds_read_probe<16><<<grid, block>>>(g.addrs, iters, g.out); break;
             case 3: step_probe<true, false, false><<<grid, block>>>(g.tables, tps, iters, g.addrs, g.out); break;
             case 4: step_probe<false, false, true><<<grid, block>>>(g.tables, tps, iters, g.addrs, g.out); break;
@@ -202,7 +250,7 @@ extern "C" int adapt_probe_run(int which, int iters, float *ms_out, double *unit
     *ms_out = best;
     const double wgs = (double)g.cus;
     switch (which) {
-        case 0: case 1: *units_out = wgs * THREADS * 8.0 * iters; break;            // lookups
+        case 0: case 1: case 6: case 7: case 8: case 9: *units_out = wgs * THREADS * 8.0 * iters; break;     // lookups
         case 2: *units_out = wgs * THREADS * 8.0 * iters * 16.0; break;             // bytes read from LDS
         case 3: *units_out = wgs * 65536.0 * iters; break;                          // bytes copied into LDS
         case 4: *units_out = wgs * 16.0 * 16.0 * iters; break;                      // matrix instructions (16 waves x 16 per step)

@@ -743,3 +743,66 @@ def test_mse_calibrator_against_direct_search_and_closed_cases():
             for k in range(8)]
     assert got == np.float32(int(np.argmin(errs)) + 1)
 
+
+
+def test_entropy_calibrator_hand_case_closed_forms_and_library_divergence():
+    """The information-loss calibrator (this build's reading of the third calibrator Sec. III-A names).
+    (1) A case small enough to work by hand: 2 bits (two magnitude levels), four bins with counts 4, 2, 1, 1.
+        Keeping two bins: p = (4, 4)/8 against q = (4, 2)/6 -> 0.5 ln 0.75 + 0.5 ln 1.5;
+        three bins: p = (4, 2, 2)/8 against q = (4, 1.5, 1.5)/7 -> 0.5 ln 0.875 + 0.5 ln(7/6);
+        four bins: p = (4, 2, 1, 1)/8 against q = (3, 3, 1, 1)/8 -> 0.5 ln(4/3) + 0.25 ln(2/3).  Three bins lose least.
+    (2) A flat histogram loses nothing only when nothing is clipped: the whole range is kept.
+    (3) A flat histogram that ends at bin k0 loses nothing from k0 on and something before: the first such k wins.
+    (4) Every loss is a Kullback-Leibler divergence: never negative, and equal to the library's value for the two
+        distributions put together here with array operations (merge by np.add.reduceat, spread by np.repeat).
+    (5) Scaling all counts changes nothing."""
+    from scipy.stats import entropy as kl_lib
+    got, kl = orc.entropy_from_histogram(np.array([4, 2, 1, 1], np.uint32), 4.0, 2, with_losses=True)
+    assert got == np.float32(3.0)
+    assert np.isinf(kl[0])
+    np.testing.assert_allclose(kl[1:], [0.0588915, 0.0103097, 0.0424747], rtol=0, atol=2e-7)
+    np.testing.assert_allclose(kl[1:], [0.5 * np.log(0.75) + 0.5 * np.log(1.5), 0.5 * np.log(0.875) + 0.5 * np.log(7 / 6),
+                                        0.5 * np.log(4 / 3) + 0.25 * np.log(2 / 3)], rtol=1e-13)
+
+    bits, bins = 4, 64                                   # eight levels
+    flat = np.full(bins, 5, np.uint32)
+    got, kl = orc.entropy_from_histogram(flat, 3.2, bits, with_losses=True)
+    assert got == np.float32(3.2) and kl[bins - 1] == 0.0 and np.all(kl[7:bins - 1] > 0)
+    ended = flat.copy()
+    ended[24:] = 0
+    width = np.float32(np.float32(3.2) / np.float32(bins))
+    got, kl = orc.entropy_from_histogram(ended, 3.2, bits, with_losses=True)
+    assert got == np.float32(np.float32(24) * width)
+    assert np.all(np.abs(kl[23:]) < 1e-15) and np.all(kl[7:23] > 0)
+
+    rng = np.random.default_rng(23)
+    for trial in range(3):
+        counts = rng.integers(0 if trial else 1, 9, bins).astype(np.uint32)
+        if trial == 2:
+            counts[:40] = (counts[:40] + 1) * 100
+            counts[40:] = 0
+            counts[63] = 1                               # one far outlier, light against the rest, behind an empty stretch
+        got, kl = orc.entropy_from_histogram(counts, 3.2, bits, with_losses=True)
+        L = 1 << (bits - 1)
+        want = np.full(bins, np.inf)
+        for k in range(L, bins + 1):
+            kept = counts[:k].astype(np.float64)
+            p = kept.copy()
+            p[-1] += counts[k:].sum()
+            edges = (np.arange(L) * k) // L
+            sizes = np.diff(np.append(edges, k))
+            sums = np.add.reduceat(kept, edges)
+            filled = np.add.reduceat((kept > 0).astype(np.float64), edges)
+            q = np.repeat(np.divide(sums, filled, out=np.zeros(L), where=filled > 0), sizes) * (kept > 0)
+            want[k - 1] = kl_lib(p, q)                   # the library normalises both and returns inf where q = 0 < p
+        assert np.all(kl[L - 1:] >= -1e-15)
+        np.testing.assert_allclose(kl[L - 1:], want[L - 1:], rtol=1e-11, atol=1e-15)
+        k_got = int(round(float(got) / float(width)))
+        assert np.float32(np.float32(k_got) * width) == got and k_got >= L
+        assert kl[k_got - 1] == np.min(kl) and np.all(kl[:k_got - 1] > kl[k_got - 1])      # the first smallest
+        if trial == 2:
+            assert k_got < bins                          # the lone outlier is clipped
+        assert orc.entropy_from_histogram(counts * np.uint32(7), 3.2, bits) == got
+    # fewer bins than levels: the only candidate keeps everything; an empty histogram keeps the range it was given
+    assert orc.entropy_from_histogram(np.array([3, 1, 2], np.uint32), 6.0, 8) == np.float32(6.0)
+    assert orc.entropy_from_histogram(np.zeros(16, np.uint32), 2.0, 4) == np.float32(2.0)
