@@ -123,6 +123,16 @@ int adapt_percentile_from_histogram(const uint32_t *counts_dev, int bins, float 
  * the centre c_j of bin j is reproduced as min(Q, rint(c_j / s)) * s; the candidate's error is sum_j counts[j] *
  * (c_j - that)^2 in fp64; the first candidate with the smallest error wins).  2 <= bits <= 16. */
 int adapt_mse_from_histogram(const uint32_t *counts_dev, int bins, float amax, int bits, float *calib_max_dev, void *stream);
+/* calib_max_dev[0] by least information loss (Sec. III-A names an entropy calibrator as the other alternative, without a
+ * definition; this one is: with L = 2^(bits-1) levels, candidate k = min(L, bins) .. bins keeps the first k bins.
+ * Reference p: the kept counts, everything beyond added to the last kept bin (where saturated values land).  Quantised q:
+ * the kept counts alone, merged into min(L, k) groups of bins [g k / L, (g+1) k / L) and spread back evenly over each
+ * group's non-empty bins.  The candidate's loss is the Kullback-Leibler divergence sum_j (p_j / P) log((p_j / P) /
+ * (q_j / Q)) over its bins with p_j > 0 (P, Q the two totals; +inf when such a bin has q_j = 0), in fp64, j ascending;
+ * the first candidate with the smallest loss wins: calib_max = k * amax / bins.  An empty histogram keeps amax.
+ * 2 <= bits <= 16. */
+int adapt_entropy_from_histogram(const uint32_t *counts_dev, int bins, float amax, int bits, float *calib_max_dev,
+                                 void *stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Approximate layers (Sec. III-B, IV): every inner-product term is one table entry.

@@ -24,7 +24,7 @@ EXPORTS = [
     "adapt_lut_create", "adapt_lut_destroy", "adapt_lut_info",
     "adapt_absmax_f32", "adapt_quantize_f32", "adapt_dequant_i32",
     "adapt_absmax_rows_f32", "adapt_quantize_rows_f32", "adapt_dequant_i32_per_channel",
-    "adapt_histogram_abs_f32", "adapt_percentile_from_histogram", "adapt_mse_from_histogram",
+    "adapt_histogram_abs_f32", "adapt_percentile_from_histogram", "adapt_mse_from_histogram", "adapt_entropy_from_histogram",
     "adapt_approx_linear", "adapt_approx_linear_noalloc", "adapt_approx_conv2d", "adapt_approx_conv_transpose2d",
     "adapt_weights_pack_linear", "adapt_weights_pack_conv2d", "adapt_weights_pack_conv_transpose2d",
     "adapt_weights_destroy", "adapt_plan_packed",
@@ -73,6 +73,7 @@ def load() -> ctypes.CDLL:
     L.adapt_histogram_abs_f32.argtypes = [vp, sz, f32, i32, vp, vp]
     L.adapt_percentile_from_histogram.argtypes = [vp, i32, f32, ctypes.c_uint, ctypes.c_uint, vp, vp]
     L.adapt_mse_from_histogram.argtypes = [vp, i32, f32, i32, vp, vp]
+    L.adapt_entropy_from_histogram.argtypes = [vp, i32, f32, i32, vp, vp]
     L.adapt_quantize_f32.argtypes = [vp, vp, sz, f32, i32, vp]
     L.adapt_lut16_create.argtypes = [ctypes.POINTER(vp), i32, vp]
     L.adapt_lut16_create_from_func.argtypes = [ctypes.POINTER(vp), i32, i32, i32]
@@ -731,6 +732,14 @@ def adapt_mse_from_histogram(counts, amax, bits, out=None, stream=None):
                                          _stream(stream)))
     return out
 
+
+
+def adapt_entropy_from_histogram(counts, amax, bits, out=None, stream=None):
+    if out is None:
+        out = torch.empty((1,), dtype=torch.float32, device=counts.device)
+    _chk(load().adapt_entropy_from_histogram(_ptr(counts, torch.int32), counts.numel(), float(amax), bits, _ptr(out, torch.float32),
+                                             _stream(stream)))
+    return out
 
 
 def adapt_ste_linear_backward_f32(dy, x, w, s_x, s_w, bits, want=("dx", "dw", "db"), out=None, stream=None):

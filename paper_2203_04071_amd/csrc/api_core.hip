@@ -210,6 +210,26 @@ int adapt_mse_from_histogram(const uint32_t *counts_dev, int bins, float amax, i
     return ADAPT_OK;
 }
 
+int adapt_entropy_from_histogram(const uint32_t *counts_dev, int bins, float amax, int bits, float *calib_max_dev, void *stream) {
+    if (bins < 1 || bins > 4096) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_entropy_from_histogram: bins=%d not in [1,4096]", bins);
+    if (!(amax > 0.0f) || bits < 2 || bits > 16) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_entropy_from_histogram: need amax > 0 and 2 <= bits <= 16");
+    if (!counts_dev || !calib_max_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_entropy_from_histogram: NULL pointer");
+    hipStream_t s = (hipStream_t)stream;
+    double *loss = nullptr;
+    HIP_TRY(dbg_malloc_async((void **)&loss, (size_t)bins * sizeof(double), s));
+    const float width = amax / (float)bins;
+    adapt::entropy_candidates_kernel<<<(unsigned)((bins + 255) / 256), 256, 0, s>>>(counts_dev, bins, 1 << (bits - 1), loss);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) {
+        adapt::mse_pick_kernel<<<1, 64, 0, s>>>(loss, bins, width, calib_max_dev);      // first smallest: calib_max = k * width
+        e = hipGetLastError();
+    }
+    hipError_t fe = hipFreeAsync(loss, s);
+    if (e != hipSuccess) return fail(ADAPT_ERR_HIP, "adapt_entropy_from_histogram: %s", hipGetErrorString(e));
+    if (fe != hipSuccess) return fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
+    return ADAPT_OK;
+}
+
 /* ------------------------------------------------------------------ fp32 operations between layers */
 
 int adapt_relu_f32(const float *x_dev, float *y_dev, size_t n, void *stream) {

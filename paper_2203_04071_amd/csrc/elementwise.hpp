@@ -204,6 +204,52 @@ static __global__ void mse_pick_kernel(const double *__restrict__ err, int bins,
     out[0] = (float)(best_k + 1) * width;
 }
 
+// Information-loss range from the histogram (the third calibrator Sec. III-A names; the definition is this library's,
+// stated in the header).  Candidate k keeps the first k bins, k = min(L, bins) .. bins with L = 2^(bits-1) levels.
+// Reference p: the kept counts with everything beyond added to the last kept bin.  Quantised q: the kept counts alone,
+// merged into min(L, k) groups [g k / L, (g+1) k / L) and spread evenly over each group's non-empty bins.  loss[k-1] =
+// sum over the kept bins with p > 0, ascending, of (p/P) log((p/P) / (q/Q)), +inf where p > 0 meets q = 0; fp64, every
+// operation rounded on its own.  One thread per candidate; loss of a k that is no candidate = +inf.  An empty
+// histogram keeps the whole range (loss 0 at k = bins only).
+static __global__ __launch_bounds__(256) void entropy_candidates_kernel(const uint32_t *__restrict__ counts, int bins, int levels,
+                                                                 double *__restrict__ loss) {
+    __shared__ uint32_t cnt[4096];
+    for (int j = threadIdx.x; j < bins; j += 256) cnt[j] = counts[j];
+    __syncthreads();
+    const int k = blockIdx.x * 256 + threadIdx.x + 1;
+    if (k > bins) return;
+    const double inf = __builtin_inf();
+    const int k_first = levels < bins ? levels : bins;
+    if (k < k_first) { loss[k - 1] = inf; return; }
+    unsigned long long total = 0, kept = 0;
+    for (int j = 0; j < bins; ++j) { total += cnt[j]; if (j < k) kept += cnt[j]; }
+    if (total == 0) { loss[k - 1] = k == bins ? 0.0 : inf; return; }
+    const unsigned long long outliers = total - kept;
+    const double P = (double)total;
+    const long long groups = levels < k ? levels : k;
+    double Q = 0.0;
+    for (long long g = 0; g < groups; ++g) {
+        const int lo = (int)(g * k / groups), hi = (int)((g + 1) * k / groups);
+        unsigned long long sg = 0; int zg = 0;
+        for (int j = lo; j < hi; ++j) { sg += cnt[j]; zg += cnt[j] > 0; }
+        if (zg) Q = Q + (double)zg * ((double)sg / (double)zg);
+    }
+    double acc = 0.0;
+    for (long long g = 0; g < groups; ++g) {
+        const int lo = (int)(g * k / groups), hi = (int)((g + 1) * k / groups);
+        unsigned long long sg = 0; int zg = 0;
+        for (int j = lo; j < hi; ++j) { sg += cnt[j]; zg += cnt[j] > 0; }
+        for (int j = lo; j < hi; ++j) {
+            const unsigned long long pj = (unsigned long long)cnt[j] + (j == k - 1 ? outliers : 0ull);
+            if (!pj) continue;
+            if (!cnt[j]) { acc = inf; continue; }
+            const double pn = (double)pj / P, qn = ((double)sg / (double)zg) / Q;
+            acc = acc + pn * log(pn / qn);
+        }
+    }
+    loss[k - 1] = acc;
+}
+
 // y = float(acc) * scale (+ bias[c]); channel of flat index i is (i / inner) % channels
 static __global__ __launch_bounds__(EW_THREADS) void dequant_kernel(const int32_t *__restrict__ acc, float *__restrict__ y,
                                                              size_t n, size_t channels, size_t inner, float scale,

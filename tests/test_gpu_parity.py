@@ -1021,6 +1021,43 @@ def test_histogram_and_percentile_bit_exact(B, n, bins):
         for bits in (4, 8, 12):
             got = host(B.adapt_mse_from_histogram(counts, amax, bits))[0]
             assert np.float32(got) == orc.mse_from_histogram(want2, amax, bits), bits
+    for bits in (4, 8, 12):
+        check_entropy_choice(B, counts, want2, amax, bits)
+
+
+def check_entropy_choice(B, counts_dev, counts, amax, bits):
+    """The information-loss calibrator picks the oracle's range; the two sides use different fp64 logarithm routines (last
+    digit may differ), so when the picks differ the oracle's loss at the kernel's pick must equal its minimum to 1e-12."""
+    got = np.float32(host(B.adapt_entropy_from_histogram(counts_dev, amax, bits))[0])
+    want, kl = orc.entropy_from_histogram(counts, amax, bits, with_losses=True)
+    if got == want:
+        return
+    bins = counts.size
+    width = np.float32(np.float32(amax) / np.float32(bins))
+    k = int(round(float(got) / float(width)))
+    assert 1 <= k <= bins and np.float32(np.float32(k) * width) == got, (got, want)
+    assert np.isfinite(kl[k - 1]) and abs(kl[k - 1] - np.min(kl)) <= 1e-12 * max(1.0, abs(np.min(kl))), (k, kl[k - 1], np.min(kl))
+
+
+@pytest.mark.parametrize("case", ["flat", "ended", "empty", "outlier", "few_bins", "hand"])
+def test_entropy_calibrator_special_histograms(B, case):
+    bits, bins, amax = 4, 64, np.float32(3.2)
+    rng = np.random.default_rng(5)
+    counts = np.full(bins, 5, np.uint32)
+    if case == "ended":
+        counts[24:] = 0
+    elif case == "empty":
+        counts[:] = 0
+    elif case == "outlier":
+        counts = ((rng.integers(0, 9, bins) + 1) * 100).astype(np.uint32)
+        counts[40:] = 0
+        counts[63] = 1
+    elif case == "few_bins":
+        counts, bits, amax = np.array([3, 1, 2], np.uint32), 8, np.float32(6.0)
+    elif case == "hand":
+        counts, bits, amax = np.array([4, 2, 1, 1], np.uint32), 2, np.float32(4.0)
+    got = np.float32(host(B.adapt_entropy_from_histogram(dev(counts.view(np.int32)), amax, bits))[0])
+    assert got == orc.entropy_from_histogram(counts, amax, bits), case
 
 
 def test_conv_layer_with_per_channel_weights_and_percentile_activations(B):
