@@ -35,6 +35,10 @@ constexpr int QUAD_LINE_BYTES = 256;
 constexpr int QUAD_BUF_BYTES = 65536;
 constexpr int QUAD_STEP = 16;           // inner indices per step
 constexpr int QUAD_ROW_SLOTS = 256;     // per workgroup: 16 waves x 16
+#ifndef ADAPT_QUAD_PF_DIST
+#define ADAPT_QUAD_PF_DIST 2
+#endif
+constexpr int QUAD_PF_DIST = ADAPT_QUAD_PF_DIST;    // the L2 prefetch runs this many steps ahead of the table being copied
 
 // the two int8 digits of entry v16 (16 bits of a table, signed or the unsigned low half of a wide one) minus digit_c
 __device__ __forceinline__ uint32_t quad_entry(uint32_t v16, int sgn, int digit_c) {
@@ -44,7 +48,10 @@ __device__ __forceinline__ uint32_t quad_entry(uint32_t v16, int sgn, int digit_
     return (uint32_t)(d0 & 0xff) | ((uint32_t)(d1 & 0xff) << 8);
 }
 
-// Derived tables in the quad order: [n_tile][step = tap * (Cp / 16) + block][line a][slot s] x 16 bytes.
+// Derived tables in the quad order: [n_tile][step = block * taps + tap][line a][slot s] x 16 bytes (block = 16 padded
+// input channels).  The taps of one block are consecutive steps: a workgroup then reads the same 16 channels of its
+// pixels (shifted by a pixel or a row) in consecutive steps, so the activation lines it needs are still in the
+// nearest caches, and the tables can stream through L2 without pushing them out.
 // wmode 0: w[n][K] / [Cout][Cin][taps]; wmode 1: [Cin][Cout][taps].  Padded channels and output channels hold the
 // digits of 0 (they add nothing; the kernel adds digit_c once per REAL lookup at the end).
 static __global__ void pack_quad_tables_kernel(const uint16_t *__restrict__ lut16, const int8_t *__restrict__ w, uint4 *__restrict__ dt,
@@ -52,8 +59,7 @@ static __global__ void pack_quad_tables_kernel(const uint16_t *__restrict__ lut1
                                                int digit_c) {
     const int lines = 1 << bits, mask = lines - 1;
     const size_t per_table = (size_t)lines * 16;
-    const int bpt = Cp / QUAD_STEP;                       // steps per tap
-    const size_t steps = (size_t)taps * bpt;
+    const size_t steps = (size_t)taps * (Cp / QUAD_STEP);
     const size_t total = (size_t)n_tiles * steps * per_table;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
@@ -62,8 +68,8 @@ static __global__ void pack_quad_tables_kernel(const uint16_t *__restrict__ lut1
         const size_t ts = i / per_table;
         const int step = (int)(ts % steps);
         const int nt = (int)(ts / steps);
-        const int tap = step / bpt;
-        const int ci = (step - tap * bpt) * QUAD_STEP + s;
+        const int blk = step / taps, tap = step - blk * taps;
+        const int ci = blk * QUAD_STEP + s;
         uint32_t e[8];
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
@@ -80,7 +86,7 @@ static __global__ void pack_quad_tables_kernel(const uint16_t *__restrict__ lut1
 }
 
 // Transposed convolution: the phase blocks of pack_line_tables_convt_kernel in the quad order,
-// [phase = ry * s + rx][n_tile][step = (m' * Tx + n') * (Cp / 16) + block][line][slot].
+// [phase = ry * s + rx][n_tile][step = block * (Ty Tx) + (m' * Tx + n')][line][slot].
 static __global__ void pack_quad_tables_convt_kernel(const uint16_t *__restrict__ lut16, const int8_t *__restrict__ w,
                                                      uint4 *__restrict__ dt, int bits, int N, int Cin, int kh, int kw, int s, int Cp,
                                                      int n_tiles, int sgn, int digit_c) {
@@ -100,8 +106,8 @@ static __global__ void pack_quad_tables_convt_kernel(const uint16_t *__restrict_
         const size_t ts = ip / per_table;
         const int step = (int)(ts % steps);
         const int nt = (int)(ts / steps);
-        const int tap = step / bpt;
-        const int ci = (step - tap * bpt) * QUAD_STEP + sl;
+        const int blk = step / (Ty * Tx), tap = step - blk * (Ty * Tx);
+        const int ci = blk * QUAD_STEP + sl;
         const int mw = tap / Tx, nw = tap - mw * Tx;
         const int ky = ry + s * (Ty - 1 - mw), kx = rx + s * (Tx - 1 - nw);
         uint32_t e[8];
@@ -190,21 +196,46 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
     // table copy: operation o of wave w moves the 1 KB chunk (o * 16 + w); tables below 16 KB use part of the lanes
     const int lanes_act = DOPS > 1 ? 64 : min(64, (int)(table_bytes >> 8));     // table_bytes / 16 waves / 16 B
     const uint64_t dma_mask = ~0ull >> (64 - lanes_act);
-    const uint32_t dma_voff = (uint32_t)(wave * lanes_act + lane) * 16u;
+    const uint32_t dma_voff = (uint32_t)lane * 16u;
+    // (8-bit tables: workgroup number `wg` starts two chunks further on than its predecessor, so that the workgroups
+    // that stream one table do not all ask L2 for the same lines at the same moment)
+    const uint32_t dma_rot = DOPS == 4 ? (uint32_t)wg * 2u : 0u;
     auto dma = [&](int step_, int buf) {
         const int step = step_ < nsteps ? step_ : nsteps - 1;       // past the end: a valid table, never read
         const unsigned char *src = dt + (size_t)(unsigned)step * table_bytes;
-        const uint32_t m0v = lds_tbl + (uint32_t)buf * QUAD_BUF_BYTES + (uint32_t)(wave * lanes_act) * 16u;
+        const uint32_t m0v = lds_tbl + (uint32_t)buf * QUAD_BUF_BYTES;
         uint64_t save;
 #pragma unroll
         for (int o = 0; o < DOPS; ++o) {
+            const uint32_t chunk = DOPS == 4 ? ((uint32_t)(o * 16 + wave) + dma_rot) & 63u : (uint32_t)(o * 16 + wave);
+            const uint32_t at = DOPS > 1 ? chunk * 1024u : (uint32_t)(wave * lanes_act) * 16u;
             asm volatile("s_mov_b64 %[sv], exec\n\ts_mov_b64 exec, %[mk]\n\t"
                          "s_mov_b32 m0, %[ma]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[vo], %[sa]\n\t"
                          "s_mov_b64 exec, %[sv]"
                          : [sv] "=&s"(save)
-                         : [vo] "v"(dma_voff), [sa] "s"(src + o * 16384), [ma] "s"(m0v + (uint32_t)o * 16384u), [mk] "s"(dma_mask)
+                         : [vo] "v"(dma_voff), [sa] "s"(src + at), [ma] "s"(m0v + at), [mk] "s"(dma_mask)
                          : "memory", "m0");
         }
+    };
+
+    // L2 prefetch.  The workgroups with the same n-tile stream the same tables at about the same time, and every table
+    // is new to the L2 they share (consecutive workgroup numbers go to consecutive XCDs, so with 8 n-tiles, or a multiple,
+    // one n-tile stays on one XCD; with 4 / 2 / 1 n-tiles every 2nd / 4th / 8th of its workgroups does).  Left alone, the
+    // first copy of every step would wait for device memory.  So each of up to 32 such workgroups touches its share of
+    // the 128-byte lines of the table QUAD_PF_DIST steps ahead with one plain load per wave (a few active addresses,
+    // result never used): the copy operations one step later then hit in L2.
+    const int pf_span = (p.n_tiles < 8 && 8 % p.n_tiles == 0) ? 8 / p.n_tiles : 1;
+    const int pf_peers = max(1, min(32, (int)(gridDim.x / (unsigned)p.n_tiles) / pf_span));
+    const int pf_share = 1 << (31 - __builtin_clz((unsigned)pf_peers));         // a power of two
+    const int pf_lines = (int)(table_bytes >> 7);
+    const int pf_per_wg = (pf_lines + pf_share - 1) / pf_share;
+    const int pf_per_wave = (pf_per_wg + 15) >> 4;                              // <= 32 (512 lines, one workgroup)
+    const uint32_t pf_voff =
+        128u * (uint32_t)min(((wg / pf_span) & (pf_share - 1)) * pf_per_wg + wave * pf_per_wave + min(lane, pf_per_wave - 1), pf_lines - 1);
+    uint32_t pf_sink = 0;
+    auto prefetch = [&](int step_) {
+        const int step = step_ < nsteps ? step_ : nsteps - 1;
+        asm volatile("global_load_dword %[d], %[vo], %[sa]" : [d] "+v"(pf_sink) : [vo] "v"(pf_voff), [sa] "s"(dt + (size_t)(unsigned)step * table_bytes));
     };
 
     // activation side: x-major addressing (as lut_lines_fast_kernel), 16 consecutive channels per step
@@ -251,27 +282,29 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
     // End of a step: this wave's part of the next table has landed (its copy operations were issued BEFORE the step's
     // activation loads, and a wave's memory operations retire in order, so all but the newest NL are done); the
     // activation loads stay in flight across the barrier and are waited for where the next step first needs them.
-    auto step_end = [&]() { asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" : : "n"(NL) : "memory"); };
+    // Per step a wave issues, in this order: DOPS copy operations, NL activation loads, one prefetch load.
+    auto step_end = [&]() { asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" : : "n"(NL + 1) : "memory"); };
     // Start of a step, after its copy operations and loads have been issued: the activations requested one step ago
-    // (the oldest NL of the DOPS + 2 NL operations in flight) have arrived.
-    auto acts_ready = [&]() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(DOPS + NL) : "memory"); };
+    // (the oldest NL of the 2 (NL + 1) + DOPS operations in flight) have arrived.
+    auto acts_ready = [&]() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(DOPS + NL + 2) : "memory"); };
 
-    // position of a step's activations: steps per tap = Cc, 16 channels = 4 channel groups of the copy each
-    const int tap0 = s_begin / p.Cc;
-    const int ky0 = tap0 / p.kw;
-    int kx = tap0 - ky0 * p.kw, bi = s_begin - tap0 * p.Cc;
+    // position of a step's activations: step = block * taps + tap (Cc blocks of 16 channels = 4 channel groups of the copy)
+    int bi = s_begin / p.taps;
+    const int tap0 = s_begin - bi * p.taps;
+    const int kh = p.taps / p.kw;
+    int ky = tap0 / p.kw, kx = tap0 - ky * p.kw;
     uint32_t choff = (uint32_t)(bi * QUAD_STEP * p.ch_stride);
-    uint32_t rowoff = (uint32_t)(ky0 * p.ky_stride);
+    uint32_t rowoff = (uint32_t)(ky * p.ky_stride);
     uint32_t tapoff = rowoff + (uint32_t)(kx * p.kx_stride);
     auto advance_step = [&]() {
-        ++bi;
-        choff += (uint32_t)(QUAD_STEP * p.ch_stride);
-        if (bi == p.Cc) {
-            bi = 0;
-            choff = 0;
-            ++kx;
-            tapoff += (uint32_t)p.kx_stride;
-            if (kx == p.kw) { kx = 0; rowoff += (uint32_t)p.ky_stride; tapoff = rowoff; }
+        ++kx;
+        tapoff += (uint32_t)p.kx_stride;
+        if (kx == p.kw) {
+            kx = 0;
+            ++ky;
+            rowoff += (uint32_t)p.ky_stride;
+            if (ky == kh) { ky = 0; rowoff = 0; choff += (uint32_t)(QUAD_STEP * p.ch_stride); }
+            tapoff = rowoff;
         }
     };
 
@@ -316,6 +349,8 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
     };
 
     // prologue: table of step 0, activations of step 0
+#pragma unroll
+    for (int d = 1; d <= QUAD_PF_DIST; ++d) prefetch(d);
     dma(0, 0);
     load_acts(actA, xt + tapoff + choff);
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" : : : "memory");
@@ -326,6 +361,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
         // even step: buffer 0; the table of the next step goes to buffer 1 and its activations are requested
         dma(s + 1, 1);
         load_acts(actB, xt + tapoff + choff);
+        prefetch(s + 1 + QUAD_PF_DIST);
         advance_step();
         acts_ready();
         run_step(std::integral_constant<int, 0>{}, actA);
@@ -334,12 +370,14 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
         // and the first activations again)
         dma(s + 2, 0);
         load_acts(actA, s + 2 < nsteps ? xt + tapoff + choff : xt);
+        prefetch(s + 2 + QUAD_PF_DIST);
         advance_step();
         acts_ready();
         run_step(std::integral_constant<int, 1>{}, actB);
         step_end();
     }
     asm volatile("s_waitcnt vmcnt(0)" : : : "memory");                      // retire what is still in flight
+    asm volatile("" : : "v"(pf_sink));
     if (s < nsteps) run_step(std::integral_constant<int, 0>{}, actA);      // odd number of steps: the last one
 
     // the last matrix instructions have to leave the pipe before a vector instruction reads their registers
