@@ -95,6 +95,37 @@ def run_probes():
                 how="probe kernels run by this script before the timed region (16 waves per compute unit; best of 3 launches each)")
 
 
+def probe_report():
+    """--probe-report: every probe of the probes library, as one JSON line (units per second and clocks per 64-lane access
+    for the LDS gathers; the figures behind the statements about gather cost in the recurrent step)."""
+    import ctypes
+    from paper_2203_04071_amd import build as hip_build
+    if not os.path.exists(hip_build.PROBES_LIB):
+        raise SystemExit("bench.py: %s is not built (python -c 'import __graft_entry__ as g; g.build()')" % hip_build.PROBES_LIB)
+    L = ctypes.CDLL(hip_build.PROBES_LIB)
+    L.adapt_probe_run.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
+    cus = L.adapt_probe_cu_count()
+    names = {0: "gather of 2-byte entries, conflict-free addresses", 1: "gather of 2-byte entries, Gaussian codes in one 512-byte row (8 bits)",
+             6: "gather of 2-byte entries, uniform codes in one 256-byte row (7 bits)",
+             7: "as 6 with two copies of the row rotated by half the banks, lanes alternating",
+             8: "gather of 1-byte entries, uniform codes in one 128-byte row", 9: "row held in registers, entries fetched with ds_bpermute",
+             2: "16-byte reads in the quad kernel's pattern (bytes)", 3: "64 KB table copies L2 -> LDS, waited for one by one (bytes)",
+             4: "v_mfma_i32_16x16x64_i8 (instructions)", 5: "copy + reads + matrix instructions of one quad step (steps x workgroups)"}
+    iters = {0: 2000, 1: 2000, 6: 2000, 7: 2000, 8: 2000, 9: 2000, 2: 1000, 3: 720, 4: 2000, 5: 720}
+    out = []
+    for which in (0, 1, 6, 7, 8, 9, 2, 3, 4, 5):
+        ms, units = ctypes.c_float(), ctypes.c_double()
+        for _ in range(2):
+            if L.adapt_probe_run(which, iters[which], ctypes.byref(ms), ctypes.byref(units)) != 0:
+                raise SystemExit("bench.py: probe %d failed" % which)
+        per_s = units.value / (ms.value * 1e-3)
+        row = dict(probe=which, what=names[which], ms=round(ms.value, 4), units_per_s=per_s)
+        if which in (0, 1, 6, 7, 8, 9):     # lookups: clocks one 64-lane gather occupies a compute unit's LDS, at 2.4 GHz
+            row["clk_per_64_lane_gather"] = round(64.0 / (per_s / (cus * 2.4e9)), 2)
+        out.append(row)
+    print(json.dumps(dict(cus=cus, clock_ghz_assumed=2.4, probes=out)))
+
+
 def _f(x):
     return np.float32(x)
 
@@ -408,6 +439,7 @@ def main():
     ap.add_argument("--prewarm-ms", type=float, default=300.0,
                     help="untimed steps for this long before the warm-up steps, so that the device clocks have settled (0: none)")
     ap.add_argument("--eager", action="store_true", help="network configurations: launch kernel by kernel instead of replaying a HIP graph")
+    ap.add_argument("--probe-report", action="store_true", help="run every ceiling probe and print their rates as one JSON line; nothing else")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run three plain 64 MiB device-to-device copies (what FETCH_SIZE / WRITE_SIZE are scaled by)")
     ap.add_argument("--traffic-bytes", type=float, default=None,
@@ -423,6 +455,9 @@ def main():
         raise SystemExit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     B.load()
     torch.cuda.set_device(0)
+    if args.probe_report:
+        probe_report()
+        return
     if args.copy_calibration:
         a = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
         b = torch.empty_like(a)
