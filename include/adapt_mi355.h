@@ -178,8 +178,11 @@ int adapt_approx_conv_transpose2d(const adapt_lut *lut, const int8_t *x_dev, con
  * Pre-packed weights (the weights of a trained layer are static; the paper expands the filters into
  * a 2-D matrix once, Sec. III-B, and generates the table offline, Sec. III-C).  Packing combines the
  * two: for every inner index k and every block of 8 output channels it stores the table entries
- * T[a][w[n][k]] for all activations a, in the order the long-matrix kernel streams them.  The handle
- * owns K * N * 2^b * 2 bytes of device memory (twice that for tables with entries beyond int16) and
+ * T[a][w[n][k]] for all activations a, in the orders the two long-matrix kernels stream them (128-byte
+ * lines; 256-byte lines of two-digit entries for the kernel that sums on the matrix pipe; both are made
+ * by the pack call, nothing is added to a handle later, so a handle may be used from several threads).
+ * The handle owns 2 * K * N * 2^b * 2 bytes of device memory, K and N rounded up to the kernels' tiles
+ * (the first order twice for tables with entries beyond int16, which only that order serves) and
  * is tied to the device, the table contents and the weight values at pack time; w_dev may be freed
  * once the stream has passed the call.  The handle keeps a pointer to `lut`: the table handle must stay alive as long
  * as the weights handle is used (short linear layers run on the whole-table kernel with pre-packed row offsets).  The packed entry points give the same integers as the plain

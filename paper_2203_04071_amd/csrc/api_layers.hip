@@ -848,7 +848,7 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
         c.cv_Ho = Ho; c.cv_Wo = Wo; c.cv_H = H; c.cv_W = W; c.cv_kh = kh; c.cv_kw = kw; c.cv_s = st; c.cv_pad = pad; c.cv_Ly = Ly; c.cv_Lx = Lx;
     }
     bool border_done = false, finished = false;
-    // a chained copy is written by the wide kernel's epilogue or, for every other kernel, by the pass that rescales afterwards
+    // a chained copy is written by the quad kernel's epilogue or, for every other kernel, by the pass that rescales afterwards
     const bool chain_ok_in_kernel = !chained || (quad && part_bytes == 0 && out_elems < 0x7fffffffull);
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io, !border && chain_ok_in_kernel, &border_done, &finished);
     rc = ws_put(ws, xt, s, rc);

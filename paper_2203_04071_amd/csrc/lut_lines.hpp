@@ -121,7 +121,7 @@ struct LinesParams {
     // the divisions every lane (rows -> image, row, column) and every wave (workgroup id -> tiles) starts with, as
     // multiply-and-shift: they were 1 - 2 us of every launch
     FastDiv d_HoWo, d_Wo, d_ntiles, d_mtiles, d_phases;
-    int corr;               // wide kernel with digit tables: added to every finished sum (see lut_wide.hpp); else 0
+    int corr;               // quad kernel (digit tables): added to every finished sum, digit_c x real lookups (lut_quad.hpp); else 0
     // Tap pairing (fast kernel, PAIRED): layers with fewer than 32 (padded) channels per tap put pair_g = 32 / Cp taps
     // side by side in a group of four steps: k-sub j serves tap pair_g * group + j / pair_cg and the four channels
     // 4 * (j % pair_cg) + step of it (pair_cg = Cp / 4).  `taps` then counts groups and Cc is 4; taps_real is the
@@ -178,7 +178,7 @@ __device__ __forceinline__ T pick4(const T *v, int i) {
 
 // Activation sources of the copy kernels: already quantised int8, or fp32 quantised on the fly with the quantiser of
 // quantize_kernel (Sec. III-A), so that a layer needs no separate quantisation pass.  The copies hold table line
-// indices (the kernels that extract a bit field do not care, the wide-line kernel relies on it).
+// indices (the kernels that extract a bit field do not care, the quad kernel relies on it).
 // byte(): the operand as a table line index, i.e. its two's-complement bits below 2^b (mask = 2^b - 1)
 // load() / code(): the two halves of byte(), for kernels that request several operands before they convert the first
 struct SrcI8 {

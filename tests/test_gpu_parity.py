@@ -530,7 +530,7 @@ def test_config2_conv_full_size(B):
 
 def test_config2_fused_layer_full_size_as_benchmarked(B):
     """The launch configuration bench.py times at config 2: one fused layer call on packed weights (quantise while the
-    input is laid out, wide-line kernel, rescaling in its epilogue), whole tensor against the oracle."""
+    input is laid out, quad kernel, rescaling in its epilogue), whole tensor against the oracle."""
     c = wl.config2()
     bits = 8
     th = orc.host_threads()
@@ -1486,7 +1486,7 @@ def test_random_grouped_layers_match_oracle(B, seed):
 
 CHAIN_CASES = [
     # N, C0, H, W, channels of three 3x3 layers, stride of the second, bits
-    (32, 64, 32, 32, (64, 64, 64), 1, 8),      # wide kernel producers and consumers (as configuration 2)
+    (32, 64, 32, 32, (64, 64, 64), 1, 8),      # quad kernel producers and consumers (as configuration 2)
     (16, 64, 8, 8, (64, 64, 64), 1, 8),        # inner dimension split over workgroups: the adding kernel writes the chain
     (8, 16, 32, 32, (16, 16, 32), 2, 8),       # paired taps, x-major; then a stride-2 consumer with a channel-last copy
     (4, 32, 16, 16, (32, 32, 32), 1, 8),       # 4 rows per lane, channel-last copies
@@ -1542,7 +1542,7 @@ def test_chained_conv_layers_match_unchained_and_oracle(B, case):
 GROUPED_LAYER_CASES = [
     # N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, groups, Cout of the 1x1 consumer (0: none)
     (2, 6, 5, 5, 6, 3, 3, 1, 1, 1, 1, 1, 1, 6, 0),
-    (3, 32, 16, 16, 32, 3, 3, 1, 1, 1, 1, 1, 1, 32, 64),      # separable block, wide consumer
+    (3, 32, 16, 16, 32, 3, 3, 1, 1, 1, 1, 1, 1, 32, 64),      # separable block, quad-kernel consumer
     (2, 24, 15, 13, 24, 5, 5, 2, 2, 2, 2, 1, 1, 24, 10),      # 5x5 stride 2, ragged; generic consumer
     (2, 8, 9, 9, 16, 3, 3, 1, 1, 1, 1, 1, 1, 8, 12),          # channel multiplier 2
     (1, 4, 8, 8, 8, 3, 3, 1, 1, 2, 2, 2, 2, 2, 0),            # 2 groups of 2 -> 4, dilated
@@ -1633,10 +1633,10 @@ def test_grouped_layer_refusals(B):
 
 
 @pytest.mark.parametrize("lo,span", [(-32768, 32895), (-16384, 32895), (-128, 32895), (-20000, 32896), (-3, 7), (-32768, 65535)])
-def test_wide_kernel_table_ranges(B, lo, span):
-    """The big-layer kernel stores table entries as two int8 digits of (entry - offset) when the table's range allows
-    (span <= 32895) and as plain int16 otherwise: tables whose entries sit at both ends of such ranges, one entry wider
-    than the limit, tiny and full int16 ranges, on a layer shape that takes that kernel; sums bit-exact either way."""
+def test_quad_kernel_table_ranges(B, lo, span):
+    """The big-layer kernel stores every table entry as two int8 digits of (entry - offset), offset = smallest entry +
+    32640, which covers any 16-bit range: tables whose entries sit at both ends of a range, ranges around the limit of the
+    kernel's predecessor (32895), tiny and full int16 ranges, on a layer shape that takes that kernel; sums bit-exact."""
     bits = 8
     rng = np.random.default_rng(abs(lo) + span)
     hi = lo + span
@@ -1663,7 +1663,7 @@ def test_wide_kernel_table_ranges(B, lo, span):
 def test_random_chains_match_oracle(B, seed):
     """Seeded random pairs of convolution layers, the first writing the second's quantised input copy in its epilogue:
     channel counts, image sizes, filter sizes, strides, paddings and table widths nobody picked by hand, so that every
-    producer kernel (wide, paired taps, generic, split sums) meets every copy layout."""
+    producer kernel (quad, paired taps, generic, split sums) meets every copy layout."""
     rng = np.random.default_rng(seed)
     bad, ran = [], 0
     th = orc.host_threads()
@@ -1722,7 +1722,7 @@ def test_random_chains_match_oracle(B, seed):
 
 CONVT_CHAIN_CASES = [
     # N, C0, H, W, (C1, k1, s1, p1), consumer ("t" transposed / "c" ordinary, C2, k2, s2, p2), bits
-    (16, 64, 8, 8, (32, 4, 2, 1), ("t", 16, 4, 2, 1), 8),      # wide kernels on both sides, borders taken off in the epilogue
+    (16, 64, 8, 8, (32, 4, 2, 1), ("t", 16, 4, 2, 1), 8),      # quad kernels on both sides, borders taken off in the epilogue
     (256, 100, 1, 1, (32, 4, 1, 0), ("t", 16, 4, 2, 1), 6),    # single input pixel (a linear layer) into a phase-form layer
     (4, 8, 5, 6, (12, 3, 2, 0), ("t", 5, 4, 2, 1), 8),         # producer in gather form (3 is no multiple of 2), ragged sizes
     (3, 7, 5, 5, (9, 2, 2, 0), ("t", 4, 2, 2, 0), 7),          # no border terms at all, generic kernels
