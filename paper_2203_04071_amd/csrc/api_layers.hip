@@ -59,6 +59,9 @@ struct adapt_weights {
     mutable struct ChainIn {
         bool valid = false;
         int N = 0, H = 0, W = 0, sh = 0, sw = 0, ph = 0, pw = 0, dh = 0, dw = 0, xmajor = 0;
+        // set by the layer that last wrote the copy: it applied ReLU before quantising, so every code is >= 0 and the
+        // quad kernel needs only the first half of every table's lines
+        bool nonneg = false;
     } chain_in;
     // linear layers only: row offsets [K][wofs_npad] for the whole-table kernel, which serves short activation matrices
     // transposed convolutions: the same for the gather form (wofs_dev, [kh kw Cin][wofs_npad]) and for the single-pixel
@@ -404,8 +407,8 @@ int launch_quad_inst(const adapt::LinesParams &p, unsigned grid, bool extra, hip
 
 template <int R>
 int launch_quad_r(const adapt::LinesParams &p, unsigned grid, bool extra, hipStream_t s) {
-    if (p.bits == 8) return launch_quad_inst<4, R>(p, grid, extra, s);
-    if (p.bits == 7) return launch_quad_inst<2, R>(p, grid, extra, s);
+    if (p.copy_lines == 256) return launch_quad_inst<4, R>(p, grid, extra, s);
+    if (p.copy_lines == 128) return launch_quad_inst<2, R>(p, grid, extra, s);
     return launch_quad_inst<1, R>(p, grid, extra, s);
 }
 
@@ -477,6 +480,7 @@ struct LinesCall {       // per-call geometry of the activation side
     // Derived tables in the quad order (lut_quad.hpp) and the offset of their digit form; needed when the plan says LK_QUAD
     const uint4 *dt_quad = nullptr;
     int quad_c = 0;
+    bool nonneg_in = false;             // every activation code is >= 0 (copy written by a ReLU epilogue)
     int32_t *partial = nullptr;         // room for the partial sums when the plan splits the inner dimension
     // transposed convolution: zero sums and geometry for taking the border terms off inside the kernel (see
     // adapt::LinesParams::zsum); run_lines reports through border_done whether it did
@@ -542,6 +546,7 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     p.d_ntiles = fast_div((uint32_t)p.n_tiles); p.d_mtiles = fast_div((uint32_t)p.m_tiles); p.d_phases = fast_div(1u);
     p.ksplit = pl.ksplit; p.gps = pl.gps; p.ks_out_stride = sums_elsewhere ? (long long)c.out_elems : 0;
     // digit tables: every real lookup of an output lacks the offset (sums wrap in 32 bits like everything else)
+    p.copy_lines = (quad && c.nonneg_in) ? (1 << bits) / 2 : (1 << bits);
     p.corr = quad ? (int)(uint32_t)((unsigned long long)((long long)q.kh * q.kw * q.Cin * (long long)c.quad_c)) : 0;
     // one base offset per lane is enough when the R rows of a lane are equally spaced in xt
     const bool regular = (c.M % R == 0) && (c.HoWo == 1 || c.Wo % R == 0);
@@ -770,7 +775,7 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     c.phases.resize(1);
     c.out_elems = out_elems; c.out_channels = (size_t)q.N; c.out_inner = (size_t)Ho * Wo;
     if (part_bytes) c.partial = reinterpret_cast<int32_t *>(xt + copy_bytes);
-    if (plan.kernel == LK_QUAD) { c.dt_quad = wh->dtq_dev; c.quad_c = wh->dtq_c; }
+    if (plan.kernel == LK_QUAD) { c.dt_quad = wh->dtq_dev; c.quad_c = wh->dtq_c; c.nonneg_in = input_ready && wh->chain_in.nonneg; }
     bool finished = false;
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io, true, nullptr, &finished);
     rc = ws_put(ws, xt, s, rc);
@@ -841,7 +846,7 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
     c.out_elems = out_elems; c.out_channels = (size_t)q.N; c.out_inner = (size_t)Ho * Wo;
     if (part_bytes) c.partial = reinterpret_cast<int32_t *>(xt + copy_bytes);
     const bool quad = plan.kernel == LK_QUAD;
-    if (quad) { c.dt_quad = wh->dtq_dev; c.quad_c = wh->dtq_c; }
+    if (quad) { c.dt_quad = wh->dtq_dev; c.quad_c = wh->dtq_c; c.nonneg_in = input_ready && wh->chain_in.nonneg; }
     const bool chained = io && io->chain.buf;
     if ((border || chained) && out_elems < 0x7fffffffull) {     // the product kernel takes the border terms off where it can; its
         if (border) c.zsum = zsum;                              // chained copy needs the true output position of a phase's pixel
@@ -1459,6 +1464,7 @@ static int conv2d_layer(const adapt_weights *h, const float *x_dev, float *y_dev
         io.chain.xmajor = ci.xmajor; io.chain.Hp = ci.H + 2 * ci.ph; io.chain.Wp = ci.W + 2 * ci.pw; io.chain.Cp = next->Cp;
         io.chain.ph = ci.ph; io.chain.pw = ci.pw;
         io.chain.scale = s_next; io.chain.Q = (float)((1 << (next->bits - 1)) - 1); io.chain.mask = (1u << next->bits) - 1u;
+        next->chain_in.nonneg = act == 1;
         io.chain_wo = (int)g.Wo;
     }
     return lines_conv2d(h->bits, h->storage, shape_of(h), h->dt_dev, nullptr, reinterpret_cast<int32_t *>(y_dev), N, H, W, (int)g.Ho,
@@ -1497,7 +1503,7 @@ int adapt_conv2d_chain_prepare(const adapt_weights *h, int N, int H, int W, int 
     HIP_TRY(hipGetLastError());
     auto &ci = h->chain_in;
     ci.N = N; ci.H = H; ci.W = W; ci.sh = stride_h; ci.sw = stride_w; ci.ph = pad_h; ci.pw = pad_w; ci.dh = dil_h; ci.dw = dil_w;
-    ci.xmajor = xmajor; ci.valid = true;
+    ci.xmajor = xmajor; ci.nonneg = false; ci.valid = true;
     return ADAPT_OK;
 }
 
@@ -1544,6 +1550,7 @@ int adapt_conv2d_grouped_layer_f32(const adapt_lut *lut, const float *x_dev, con
         io.chain.xmajor = ci.xmajor; io.chain.Hp = ci.H + 2 * ci.ph; io.chain.Wp = ci.W + 2 * ci.pw; io.chain.Cp = next->Cp;
         io.chain.ph = ci.ph; io.chain.pw = ci.pw;
         io.chain.scale = s_next; io.chain.Q = (float)((1 << (next->bits - 1)) - 1); io.chain.mask = (1u << next->bits) - 1u;
+        next->chain_in.nonneg = act == 1;
         io.chain_wo = (int)Wo;
     }
     return run_grouped(lut, nullptr, w_dev, reinterpret_cast<int32_t *>(y_dev), N, Cin, H, W, Cout, (int)Ho, (int)Wo, kh, kw, stride_h,
@@ -1615,7 +1622,7 @@ int adapt_conv_transpose2d_chain_prepare(const adapt_weights *h, int N, int H, i
     HIP_TRY(hipGetLastError());
     auto &ci = h->chain_in;
     ci.N = N; ci.H = H; ci.W = W; ci.sh = ci.sw = st; ci.ph = Ty - 1; ci.pw = Tx - 1; ci.dh = ci.dw = pad;     // (dh, dw: the layer's padding)
-    ci.xmajor = xmajor; ci.valid = true;
+    ci.xmajor = xmajor; ci.nonneg = false; ci.valid = true;
     return ADAPT_OK;
 }
 
@@ -1660,6 +1667,7 @@ int adapt_conv_transpose2d_layer_chain_f32(const adapt_weights *h, const float *
         io.chain.xmajor = ci.xmajor; io.chain.Hp = ci.H + 2 * ci.ph; io.chain.Wp = ci.W + 2 * ci.pw; io.chain.Cp = next->Cp;
         io.chain.ph = ci.ph; io.chain.pw = ci.pw;
         io.chain.scale = s_next; io.chain.Q = (float)((1 << (next->bits - 1)) - 1); io.chain.mask = (1u << next->bits) - 1u;
+        next->chain_in.nonneg = act == 1;
         io.chain_wo = (int)Wo;
     }
     hipStream_t s = (hipStream_t)stream;

@@ -121,6 +121,8 @@ struct LinesParams {
     // the divisions every lane (rows -> image, row, column) and every wave (workgroup id -> tiles) starts with, as
     // multiply-and-shift: they were 1 - 2 us of every launch
     FastDiv d_HoWo, d_Wo, d_ntiles, d_mtiles, d_phases;
+    int copy_lines;         // quad kernel: lines of every table that are copied into LDS (all 2^bits, or the first half when
+                            // the activations are known to be >= 0: their codes then never select the other half)
     int corr;               // quad kernel (digit tables): added to every finished sum, digit_c x real lookups (lut_quad.hpp); else 0
     // Tap pairing (fast kernel, PAIRED): layers with fewer than 32 (padded) channels per tap put pair_g = 32 / Cp taps
     // side by side in a group of four steps: k-sub j serves tap pair_g * group + j / pair_cg and the four channels

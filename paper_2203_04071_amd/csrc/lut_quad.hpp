@@ -157,8 +157,8 @@ __device__ __forceinline__ void quad_add(i32x4_t &d, u32x4_t &v, const i32x4_t &
                  : [v] "v"(v), [a] "v"(a), [wn] "n"(WAITN));
 }
 
-// DOPS: table copy operations per wave and step = 2^b * 256 B / (16 waves * 1 KB): 4 / 2 / 1 for b = 8 / 7 / <= 6
-// (smaller tables: one operation with fewer lanes).  R: rows (consecutive output pixels) per row slot, 8 or 4: a
+// DOPS: table copy operations per wave and step = copied lines * 256 B / (16 waves * 1 KB): 4 / 2 / 1 for 256 / 128 /
+// <= 64 lines (fewer: one operation with fewer lanes).  R: rows (consecutive output pixels) per row slot, 8 or 4: a
 // workgroup owns 256 R rows.  EXTRA: the epilogue also knows tanh, the border terms of a transposed convolution and the
 // next layer's quantised input copy.
 // Launch parameters as for the lines kernels, with these readings: Cc = steps per tap (padded channels / 16);
@@ -185,7 +185,8 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
     const int out_off = pick4(p.out_off, ph);
     int32_t *const outp = p.out + (size_t)ks * p.ks_out_stride;
     const int lines = 1 << p.bits;
-    const uint32_t table_bytes = (uint32_t)lines * QUAD_LINE_BYTES;
+    const uint32_t table_bytes = (uint32_t)lines * QUAD_LINE_BYTES;          // distance between the tables of two steps
+    const uint32_t copy_bytes = (uint32_t)p.copy_lines * QUAD_LINE_BYTES;    // what a step brings into LDS (DOPS covers it)
     const int steps_all = p.taps * p.Cc;
     const int s_begin = ks * p.gps;
     const int nsteps = min(steps_all, s_begin + p.gps) - s_begin;
@@ -194,7 +195,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
     const uint32_t lds_tbl = (uint32_t)(uintptr_t)(lds_void_ptr)tbl;
 
     // table copy: operation o of wave w moves the 1 KB chunk (o * 16 + w); tables below 16 KB use part of the lanes
-    const int lanes_act = DOPS > 1 ? 64 : min(64, (int)(table_bytes >> 8));     // table_bytes / 16 waves / 16 B
+    const int lanes_act = DOPS > 1 ? 64 : min(64, (int)(copy_bytes >> 8));      // copy_bytes / 16 waves / 16 B
     const uint64_t dma_mask = ~0ull >> (64 - lanes_act);
     const uint32_t dma_voff = (uint32_t)lane * 16u;
     // (8-bit tables: workgroup number `wg` starts two chunks further on than its predecessor, so that the workgroups
@@ -227,7 +228,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
     const int pf_span = (p.n_tiles < 8 && 8 % p.n_tiles == 0) ? 8 / p.n_tiles : 1;
     const int pf_peers = max(1, min(32, (int)(gridDim.x / (unsigned)p.n_tiles) / pf_span));
     const int pf_share = 1 << (31 - __builtin_clz((unsigned)pf_peers));         // a power of two
-    const int pf_lines = (int)(table_bytes >> 7);
+    const int pf_lines = (int)(copy_bytes >> 7);
     const int pf_per_wg = (pf_lines + pf_share - 1) / pf_share;
     const int pf_per_wave = (pf_per_wg + 15) >> 4;                              // <= 32 (512 lines, one workgroup)
     const uint32_t pf_voff =

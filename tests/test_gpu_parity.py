@@ -1539,6 +1539,39 @@ def test_chained_conv_layers_match_unchained_and_oracle(B, case):
             assert bits_equal(host(outs[i]), acts[i + 1]), (rep, i)
 
 
+@pytest.mark.parametrize("bits", [8, 7, 5])
+def test_chained_consumer_after_relu_and_after_no_activation(B, bits):
+    """A consumer on the big-layer kernel copies only the first half of every table into LDS when the producing layer
+    applied ReLU (all codes >= 0) and the whole table otherwise: the same two handles, the producer alternating between no
+    activation (negative codes present) and ReLU, consumer output against the oracle every time."""
+    N, C, H, W = 32, 64, 32, 32
+    rng = np.random.default_rng(900 + bits)
+    lut = wl.make_lut(bits)
+    L = B.Lut(lut, bits)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    w0 = wl.random_i8(rng, (C, C, 3, 3), bits, "gauss")
+    w1 = wl.random_i8(rng, (C, C, 3, 3), bits, "gauss")
+    th = orc.host_threads()
+    s0 = orc.scale_from_amax(orc.absmax(x), bits)
+    acc0 = orc.approx_conv2d(lut, bits, orc.quantize(x, s0, bits), w0, (1, 1), (1, 1), threads=th)
+    y0 = orc.dequant(acc0, np.float32(s0) * np.float32(0.01), N, C, H * W)
+    p0, p1 = B.adapt_weights_pack_conv2d(L, dev(w0)), B.adapt_weights_pack_conv2d(L, dev(w1))
+    B.adapt_conv2d_chain_prepare(p1, N, H, W, (1, 1), (1, 1))
+    o0 = torch.empty((N, C, H, W), dtype=torch.float32, device="cuda")
+    o1 = torch.empty((N, C, H, W), dtype=torch.float32, device="cuda")
+    for act in (B.ACT_NONE, B.ACT_RELU, B.ACT_NONE, B.ACT_RELU):
+        mid = np.maximum(y0, 0) if act == B.ACT_RELU else y0
+        s1 = orc.scale_from_amax(orc.absmax(mid), bits)
+        q1 = orc.quantize(mid, s1, bits)
+        assert (q1 < 0).any() == (act == B.ACT_NONE)
+        acc1 = orc.approx_conv2d(lut, bits, q1, w1, (1, 1), (1, 1), threads=th)
+        want = orc.dequant(acc1, np.float32(s1) * np.float32(0.01), N, C, H * W)
+        B.adapt_conv2d_layer_chain_f32(p0, dev(x), s0, np.float32(s0) * np.float32(0.01), o0, (1, 1), (1, 1), act=act, next_pw=p1, s_next=s1)
+        B.adapt_conv2d_layer_chain_f32(p1, None, s1, np.float32(s1) * np.float32(0.01), o1, (1, 1), (1, 1), in_shape=(N, H, W))
+        assert bits_equal(host(o0), mid), act
+        assert bits_equal(host(o1), want), act
+
+
 GROUPED_LAYER_CASES = [
     # N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, groups, Cout of the 1x1 consumer (0: none)
     (2, 6, 5, 5, 6, 3, 3, 1, 1, 1, 1, 1, 1, 6, 0),
