@@ -227,13 +227,16 @@ int adapt_approx_conv2d_packed(const adapt_weights *w, const int8_t *x_dev, int3
 int adapt_approx_conv_transpose2d_packed(const adapt_weights *w, const int8_t *x_dev, int32_t *acc_dev, int N, int H, int W,
                                          int pad, void *stream);
 
-/* A grouped convolution whose groups have fewer than 8 output channels (depthwise: groups = Cin, the first half of the
- * separable convolution, eq. (1)) as one call and one kernel: x is quantised with s_x while it is staged, the sums are
- * rescaled as in adapt_conv2d_layer_f32 (s_out or s_out_vec_dev, bias, act) and written to y_dev (fp32 [N][Cout][Ho][Wo];
- * may be NULL when `next` is given), and, when `next` != NULL (a prepared conv2d handle, e.g. the pointwise half), also
- * as next's quantised input copy as in adapt_conv2d_layer_chain_f32.  w_dev int8 [Cout][Cin/groups][kh][kw].  Shapes
- * whose input rows do not fit the kernel's staging buffer, other group sizes and two-pass tables return
- * ADAPT_ERR_UNSUPPORTED (use the separate calls). */
+/* A grouped convolution as one call (Sec. III-B; depthwise: groups = Cin, the first half of the separable convolution,
+ * eq. (1)).  The sums are rescaled as in adapt_conv2d_layer_f32 (s_out or s_out_vec_dev, bias, act) and written to y_dev
+ * (fp32 [N][Cout][Ho][Wo]) and, when `next` != NULL (a prepared conv2d handle, e.g. the pointwise half), also as next's
+ * quantised input copy as in adapt_conv2d_layer_chain_f32.  w_dev int8 [Cout][Cin/groups][kh][kw].
+ *   Groups with fewer than 8 output channels: one kernel, x is quantised with s_x while it is staged; y_dev may be NULL
+ *     when `next` is given.  Shapes whose input rows do not fit the kernel's staging buffer and two-pass tables return
+ *     ADAPT_ERR_UNSUPPORTED (use the separate calls).
+ *   Groups with 8 or more output channels (groups = 1 included): the quantiser, then the whole-table product kernel over
+ *     a group dimension with the finishing pass in its epilogue (single-pass table, no tanh, no `next`) or in place
+ *     afterwards; y_dev is required; the quantised input lives in a stream-ordered temporary. */
 int adapt_conv2d_grouped_layer_f32(const adapt_lut *lut, const float *x_dev, const int8_t *w_dev, float *y_dev, int N,
                                    int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w,
                                    int pad_h, int pad_w, int dil_h, int dil_w, int groups, float s_x, float s_out,
@@ -418,6 +421,22 @@ int adapt_approx_linear_func_i16(int kind, int param, int bits, const int16_t *a
 int adapt_approx_conv2d_func_i16(int kind, int param, int bits, const int16_t *x_dev, const int16_t *w_dev,
                                  int32_t *acc_dev, int N, int Cin, int H, int W, int Cout, int kh, int kw,
                                  int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, void *stream);
+
+/* Whole layers on operands of up to 16 bits (Sec. III-A quantiser, the products above, Sec. III-A rescaling), one call each:
+ *     q   = quantise(x, s_x, bits)                      exactly as adapt_quantize_i16_f32 (stream-ordered temporary)
+ *     acc = product of q with w_dev                     exactly as the *_i16 / *_func_i16 entry points above
+ *     y   = float(acc) * s_out (or s_out_vec_dev[n]), + bias_dev[n] if given, then act (0 none, 1 ReLU, 2 tanh)
+ * with the last step in the product kernel's epilogue (two kernels per call).  lut != NULL: table form, `bits` is the
+ * table's and kind / param / bits are ignored; lut == NULL: the function form (kind, param, bits) as in
+ * adapt_approx_linear_func_i16.  x_dev fp32 [M][K] / [N][Cin][H][W]; w_dev int16 codes [N][K] / [Cout][Cin][kh][kw];
+ * y_dev fp32 [M][N] / [N][Cout][Ho][Wo]. */
+int adapt_linear_layer_i16_f32(const adapt_lut16 *lut, int kind, int param, int bits, const float *x_dev, const int16_t *w_dev,
+                               float *y_dev, int M, int K, int N, float s_x, float s_out, const float *s_out_vec_dev,
+                               const float *bias_dev, int act, void *stream);
+int adapt_conv2d_layer_i16_f32(const adapt_lut16 *lut, int kind, int param, int bits, const float *x_dev, const int16_t *w_dev,
+                               float *y_dev, int N, int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w,
+                               int pad_h, int pad_w, int dil_h, int dil_w, float s_x, float s_out, const float *s_out_vec_dev,
+                               const float *bias_dev, int act, void *stream);
 
 /* ------------------------------------------------------------------ retraining: backward pass */
 

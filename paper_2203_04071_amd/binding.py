@@ -36,6 +36,7 @@ EXPORTS = [
     "adapt_tanh_f32", "adapt_sigmoid_f32", "adapt_lstm_cell_f32", "adapt_lstm_cell_q_f32", "adapt_lstm_step_f32", "adapt_gru_step_f32", "adapt_rnn_step_f32", "adapt_gru_cell_f32", "adapt_rnn_cell_f32",
     "adapt_lut16_create", "adapt_lut16_create_from_func", "adapt_lut16_destroy", "adapt_lut16_bits", "adapt_quantize_i16_f32",
     "adapt_approx_linear_i16", "adapt_approx_conv2d_i16", "adapt_approx_linear_func_i16", "adapt_approx_conv2d_func_i16",
+    "adapt_linear_layer_i16_f32", "adapt_conv2d_layer_i16_f32",
     "adapt_ste_linear_backward_f32", "adapt_sgd_step_f32", "adapt_relu_backward_f32", "adapt_ste_conv2d_backward_workspace", "adapt_ste_conv2d_backward_f32",
 ]
 
@@ -84,6 +85,8 @@ def load() -> ctypes.CDLL:
     L.adapt_approx_conv2d_i16.argtypes = [vp, vp, vp, vp] + [i32] * 13 + [vp]
     L.adapt_approx_linear_func_i16.argtypes = [i32, i32, i32, vp, vp, vp, i32, i32, i32, vp]
     L.adapt_approx_conv2d_func_i16.argtypes = [i32, i32, i32, vp, vp, vp] + [i32] * 13 + [vp]
+    L.adapt_linear_layer_i16_f32.argtypes = [vp, i32, i32, i32, vp, vp, vp, i32, i32, i32, f32, f32, vp, vp, i32, vp]
+    L.adapt_conv2d_layer_i16_f32.argtypes = [vp, i32, i32, i32, vp, vp, vp] + [i32] * 13 + [f32, f32, vp, vp, i32, vp]
     L.adapt_dequant_i32.argtypes = [vp, vp, sz, sz, sz, f32, vp, vp]
     L.adapt_approx_linear.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
     L.adapt_approx_linear_noalloc.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
@@ -553,6 +556,35 @@ def _scales(s_out):
     return float(s_out), None
 
 
+def adapt_linear_layer_i16_f32(mul, x, w, s_x, s_out, bias=None, act=ACT_NONE, out=None, stream=None):
+    """mul: a Lut16 (table form) or a tuple (kind, param, bits) (function form)."""
+    M, K = x.shape
+    N, K2 = w.shape
+    assert K == K2
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=x.device)
+    lut, (kind, param, bits) = (mul.handle, (0, 0, 0)) if isinstance(mul, Lut16) else (None, mul)
+    sc, sv = _scales(s_out)
+    _chk(load().adapt_linear_layer_i16_f32(lut, kind, param, bits, _ptr(x, torch.float32), _ptr(w, torch.int16), _ptr(out, torch.float32),
+                                           M, K, N, float(s_x), sc, sv, _ptr(bias, torch.float32), act, _stream(stream)))
+    return out
+
+
+def adapt_conv2d_layer_i16_f32(mul, x, w, s_x, s_out, stride=(1, 1), pad=(0, 0), dil=(1, 1), bias=None, act=ACT_NONE, out=None, stream=None):
+    N, Cin, H, W = x.shape
+    Cout, Cin2, kh, kw = w.shape
+    assert Cin == Cin2
+    if out is None:
+        Ho, Wo = conv_out_hw(H, W, kh, kw, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1])
+        out = torch.empty((N, Cout, Ho, Wo), dtype=torch.float32, device=x.device)
+    lut, (kind, param, bits) = (mul.handle, (0, 0, 0)) if isinstance(mul, Lut16) else (None, mul)
+    sc, sv = _scales(s_out)
+    _chk(load().adapt_conv2d_layer_i16_f32(lut, kind, param, bits, _ptr(x, torch.float32), _ptr(w, torch.int16), _ptr(out, torch.float32),
+                                           N, Cin, H, W, Cout, kh, kw, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1],
+                                           float(s_x), sc, sv, _ptr(bias, torch.float32), act, _stream(stream)))
+    return out
+
+
 def adapt_linear_layer_f32(pw: PackedWeights, x, s_x, s_out, bias=None, act=ACT_NONE, out=None, stream=None):
     M, K = x.shape
     N, K2 = pw.shape
@@ -604,7 +636,8 @@ def adapt_conv2d_layer_chain_f32(pw: PackedWeights, x, s_x, s_out, out, stride=(
 
 def adapt_conv2d_grouped_layer_f32(lut: Lut, x, w, s_x, s_out, stride=(1, 1), pad=(0, 0), dil=(1, 1), groups=1, bias=None, act=ACT_NONE,
                                    out=None, want_out=True, next_pw: PackedWeights = None, s_next: float = 1.0, stream=None):
-    """Depthwise-style grouped convolution as one kernel (fp32 in; fp32 out and / or the next layer's input copy)."""
+    """Grouped convolution as one call (fp32 in; fp32 out and / or the next layer's input copy): one kernel for groups of fewer than
+    8 output channels, quantiser + whole-table kernel for larger groups (these need the fp32 output)."""
     N, Cin, H, W = x.shape
     Cout, cg, kh, kw = w.shape
     if out is None and want_out:

@@ -104,9 +104,19 @@ int adapt_quantize_i16_f32(const float *x_dev, int16_t *q_dev, size_t n, float s
 
 namespace {
 
+// whole-layer form: the finishing pass of the product kernel
+struct BigLayer {
+    float s_out = 1.0f;
+    const float *s_out_vec = nullptr, *bias = nullptr;
+    int act = 0;
+};
+
 // table form: lut != nullptr; function form: lut == nullptr and (kind, param)
-int run_big(const adapt_lut16 *lut, int kind, int param, const int16_t *x, const int16_t *w, int32_t *out, adapt::BigParams p, hipStream_t s) {
+int run_big(const adapt_lut16 *lut, int kind, int param, const int16_t *x, const int16_t *w, int32_t *out, adapt::BigParams p, hipStream_t s,
+            const BigLayer *layer = nullptr) {
     if (p.M == 0 || p.N == 0) return ADAPT_OK;
+    p.deq = layer ? 1 : 0; p.act = layer ? layer->act : 0; p.scale = layer ? layer->s_out : 1.0f;
+    p.scales = layer ? layer->s_out_vec : nullptr; p.bias = layer ? layer->bias : nullptr;
     const long long K = (long long)p.taps * p.Cin;
     const int NT = lut ? adapt::BIG_NT_TABLE : adapt::BIG_NT_FUNC, threads = lut ? adapt::BIG_THREADS_TABLE : adapt::BIG_THREADS_FUNC;
     p.Npad = (p.N + NT - 1) / NT * NT;
@@ -146,7 +156,7 @@ int run_big(const adapt_lut16 *lut, int kind, int param, const int16_t *x, const
 }
 
 int big_linear(const char *who, const adapt_lut16 *lut, int kind, int param, const int16_t *a, const int16_t *w, int32_t *acc, int M,
-               int K, int N, void *stream) {
+               int K, int N, void *stream, const BigLayer *layer = nullptr) {
     if (M < 0 || K < 0 || N < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: negative dimension", who);
     if (M == 0 || N == 0) return ADAPT_OK;
     if (!acc || (K > 0 && (!a || !w))) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
@@ -156,11 +166,12 @@ int big_linear(const char *who, const adapt_lut16 *lut, int kind, int param, con
     p.M = M; p.N = N; p.conv = 0; p.Cin = K; p.taps = 1; p.kw = 1;
     p.H = p.W = p.Wo = p.HoWo = 1; p.sh = p.sw = p.dh = p.dw = 1; p.ph = p.pw = 0;
     p.kstride = 1; p.img_stride = K;
-    return run_big(lut, kind, param, a, w, acc, p, (hipStream_t)stream);
+    return run_big(lut, kind, param, a, w, acc, p, (hipStream_t)stream, layer);
 }
 
 int big_conv2d(const char *who, const adapt_lut16 *lut, int kind, int param, const int16_t *x, const int16_t *w, int32_t *acc, int N,
-               int Cin, int H, int W, int Cout, int kh, int kw, int sh, int sw, int ph, int pw, int dh, int dw, void *stream) {
+               int Cin, int H, int W, int Cout, int kh, int kw, int sh, int sw, int ph, int pw, int dh, int dw, void *stream,
+               const BigLayer *layer = nullptr) {
     if (N < 0 || Cin < 1 || H < 1 || W < 1 || Cout < 1 || kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0 || dh < 1 || dw < 1)
         return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
     const long long eh = (long long)H + 2LL * ph - (long long)dh * (kh - 1) - 1, ew = (long long)W + 2LL * pw - (long long)dw * (kw - 1) - 1;
@@ -176,7 +187,7 @@ int big_conv2d(const char *who, const adapt_lut16 *lut, int kind, int param, con
     p.H = H; p.W = W; p.Wo = (int)Wo; p.HoWo = (int)(Ho * Wo);
     p.sh = sh; p.sw = sw; p.ph = ph; p.pw = pw; p.dh = dh; p.dw = dw;
     p.kstride = H * W; p.img_stride = Cin * H * W;
-    return run_big(lut, kind, param, x, w, acc, p, (hipStream_t)stream);
+    return run_big(lut, kind, param, x, w, acc, p, (hipStream_t)stream, layer);
 }
 
 }  // namespace
@@ -211,6 +222,66 @@ int adapt_approx_conv2d_func_i16(int kind, int param, int bits, const int16_t *x
     if (rc) return rc;
     return big_conv2d("adapt_approx_conv2d_func_i16", nullptr, kind, param, x_dev, w_dev, acc_dev, N, Cin, H, W, Cout, kh, kw, stride_h,
                       stride_w, pad_h, pad_w, dil_h, dil_w, stream);
+}
+
+
+/* ------------------------------------------------------------------ whole layers on operands of up to 16 bits */
+
+}  // extern "C"
+
+namespace {
+
+// lut != NULL: table form (its bits); else the function (kind, param) at `bits`.  Quantises x into a stream-ordered
+// temporary, then runs the product with the finishing pass in its epilogue.
+template <class Product>
+int i16_layer(const char *who, const adapt_lut16 *lut, int kind, int param, int bits, const float *x_dev, size_t n_in, float s_x, float s_out,
+              const float *s_out_vec_dev, const float *bias_dev, int act, hipStream_t s, Product product) {
+    if (lut) bits = lut->bits;
+    else if (int rc = func_args(who, kind, param, bits, 16)) return rc;
+    if (act < 0 || act > 2) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: act=%d not in {0, 1, 2}", who, act);
+    if (!(s_x > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: s_x must be > 0", who);
+    BigLayer layer;
+    layer.s_out = s_out; layer.s_out_vec = s_out_vec_dev; layer.bias = bias_dev; layer.act = act;
+    if (n_in == 0) return product(nullptr, layer);      // (no inner dimension: the sums are 0, the finishing pass still runs)
+    if (!x_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
+    int16_t *q = nullptr;
+    HIP_TRY(dbg_malloc_async((void **)&q, n_in * sizeof(int16_t), s));
+    adapt::quantize_i16_kernel<<<ew_grid(n_in), 256, 0, s>>>(x_dev, q, n_in, s_x, (float)((1 << (bits - 1)) - 1));
+    hipError_t qe = hipGetLastError();
+    int rc = qe == hipSuccess ? ADAPT_OK : fail(ADAPT_ERR_HIP, "%s: quantise launch: %s", who, hipGetErrorString(qe));
+    if (rc == ADAPT_OK) rc = product(q, layer);
+    hipError_t fe = hipFreeAsync(q, s);
+    if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
+    return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+int adapt_linear_layer_i16_f32(const adapt_lut16 *lut, int kind, int param, int bits, const float *x_dev, const int16_t *w_dev, float *y_dev,
+                               int M, int K, int N, float s_x, float s_out, const float *s_out_vec_dev, const float *bias_dev, int act,
+                               void *stream) {
+    const char *who = "adapt_linear_layer_i16_f32";
+    if (M < 0 || K < 0 || N < 0) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: negative dimension", who);
+    return i16_layer(who, lut, kind, param, bits, x_dev, (size_t)M * K, s_x, s_out, s_out_vec_dev, bias_dev, act, (hipStream_t)stream,
+                     [&](const int16_t *q, const BigLayer &layer) {
+                         return big_linear(who, lut, kind, param, q, w_dev, reinterpret_cast<int32_t *>(y_dev), M, K, N, stream, &layer);
+                     });
+}
+
+int adapt_conv2d_layer_i16_f32(const adapt_lut16 *lut, int kind, int param, int bits, const float *x_dev, const int16_t *w_dev, float *y_dev,
+                               int N, int Cin, int H, int W, int Cout, int kh, int kw, int stride_h, int stride_w, int pad_h, int pad_w,
+                               int dil_h, int dil_w, float s_x, float s_out, const float *s_out_vec_dev, const float *bias_dev, int act,
+                               void *stream) {
+    const char *who = "adapt_conv2d_layer_i16_f32";
+    if (N < 0 || Cin < 1 || H < 1 || W < 1) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: bad dimension", who);
+    return i16_layer(who, lut, kind, param, bits, x_dev, (size_t)N * Cin * H * W, s_x, s_out, s_out_vec_dev, bias_dev, act, (hipStream_t)stream,
+                     [&](const int16_t *q, const BigLayer &layer) {
+                         if (N == 0) return (int)ADAPT_OK;
+                         return big_conv2d(who, lut, kind, param, q, w_dev, reinterpret_cast<int32_t *>(y_dev), N, Cin, H, W, Cout, kh, kw,
+                                           stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, stream, &layer);
+                     });
 }
 
 }  // extern "C"

@@ -1535,8 +1535,10 @@ int adapt_conv2d_grouped_layer_f32(const adapt_lut *lut, const float *x_dev, con
     if (!x_dev || !w_dev || (!y_dev && !next)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
     if ((long long)N * Cout * Ho * Wo > 0x7fffffffLL || (long long)N * Cin * H * W > 0x7fffffffLL)
         return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
-    if (groups == 1 || Cout / groups >= 8)
-        return fail(ADAPT_ERR_UNSUPPORTED, "%s: only groups with fewer than 8 output channels each (depthwise and relatives)", who);
+    const bool wide_groups = Cout / groups >= 8 || groups == 1;     // whole-table kernel over a group dimension instead of the tiled kernel
+    if (wide_groups && !y_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: groups of 8 or more output channels need y_dev (the sums are finished in place)", who);
+    if (wide_groups && ((long long)N * Ho * Wo > 0x7fffffffLL || (long long)Cout * (Cin / groups) * kh * kw > 0x7fffffffLL))
+        return fail(ADAPT_ERR_UNSUPPORTED, "%s: tensor with more than 2^31-1 elements", who);
     LayerIO io;
     io.xf = x_dev; io.s_x = s_x; io.Q = (float)((1 << (lut->bits - 1)) - 1);
     io.deq = 1; io.act = act; io.s_out = s_out; io.s_out_vec = s_out_vec_dev; io.bias = bias_dev;
@@ -1552,6 +1554,29 @@ int adapt_conv2d_grouped_layer_f32(const adapt_lut *lut, const float *x_dev, con
         io.chain.scale = s_next; io.chain.Q = (float)((1 << (next->bits - 1)) - 1); io.chain.mask = (1u << next->bits) - 1u;
         next->chain_in.nonneg = act == 1;
         io.chain_wo = (int)Wo;
+    }
+    if (wide_groups) {
+        // quantise into a stream-ordered temporary, then the product of adapt_approx_conv2d with the layer's finishing
+        // pass (inside the product kernel when it can, else in place afterwards, which also writes next's copy)
+        hipStream_t s = (hipStream_t)stream;
+        const size_t n = (size_t)N * Cin * H * W;
+        int8_t *q8 = nullptr;
+        HIP_TRY(dbg_malloc_async((void **)&q8, n + 64, s));
+        adapt::quantize_kernel<<<ew_grid(n / 16 + 1), adapt::EW_THREADS, 0, s>>>(x_dev, q8, n, s_x, io.Q, (aligned16(x_dev) && aligned16(q8)) ? 1 : 0);
+        hipError_t qe = hipGetLastError();
+        rc = qe == hipSuccess ? ADAPT_OK : fail(ADAPT_ERR_HIP, "%s: quantise launch: %s", who, hipGetErrorString(qe));
+        if (rc == ADAPT_OK) {
+            Geometry g{};
+            g.mode = adapt::MODE_CONV; g.M = (int)(N * Ho * Wo); g.N = Cout / groups; g.Cin = Cin / groups; g.taps = kh * kw; g.kw = kw;
+            g.H = H; g.W = W; g.Wo = (int)Wo; g.HoWo = (int)(Ho * Wo);
+            g.sh = stride_h; g.sw = stride_w; g.ph = pad_h; g.pw = pad_w; g.dh = dil_h; g.dw = dil_w;
+            g.kstride = H * W; g.img_stride = Cin * H * W; g.groups = groups;
+            io.xf = nullptr;
+            rc = run_rows(lut, q8, w_dev, reinterpret_cast<int32_t *>(y_dev), g, s, nullptr, 0, &io);
+        }
+        hipError_t fe = hipFreeAsync(q8, s);
+        if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
+        return rc;
     }
     return run_grouped(lut, nullptr, w_dev, reinterpret_cast<int32_t *>(y_dev), N, Cin, H, W, Cout, (int)Ho, (int)Wo, kh, kw, stride_h,
                        stride_w, pad_h, pad_w, dil_h, dil_w, groups, (hipStream_t)stream, &io);

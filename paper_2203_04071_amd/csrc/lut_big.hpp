@@ -15,6 +15,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "elementwise.hpp"
+
 namespace adapt {
 
 // function form: 256 lanes, 8 channels per lane (the weight-side arithmetic is shared by the wave, the activation-side
@@ -103,7 +105,21 @@ struct BigParams {
     int H, W, Wo, HoWo;     // GEMM: HoWo = Wo = 1
     int sh, sw, ph, pw, dh, dw;
     int kstride, img_stride;
+    // whole-layer form: deq != 0 stores fp32 y = float(acc) * scale (or scales[n]), + bias[n] if bias, then ReLU (act 1) or
+    // tanh (act 2) instead of the integer sum
+    int deq, act;
+    float scale;
+    const float *scales, *bias;
 };
+
+__device__ __forceinline__ uint32_t big_finish(const BigParams &p, uint32_t v, int n) {
+    if (!p.deq) return v;
+    float y = (float)(int32_t)v * (p.scales ? p.scales[n] : p.scale);
+    if (p.bias) y = y + p.bias[n];
+    if (p.act == 1) y = y > 0.0f ? y : 0.0f;
+    else if (p.act == 2) y = tanh_spec(y);
+    return __float_as_uint(y);
+}
 
 template <class Mul, int NT, int THREADS, bool IN_STEP>
 __global__ __launch_bounds__(THREADS) void big_rows_kernel(const BigParams p, const Mul mul) {
@@ -163,7 +179,7 @@ __global__ __launch_bounds__(THREADS) void big_rows_kernel(const BigParams p, co
         int32_t *o = p.out + (size_t)img * p.N * p.HoWo + pix;
 #pragma unroll
         for (int n = 0; n < NT; ++n)
-            if (n0 + n < p.N) o[(size_t)(n0 + n) * p.HoWo] = (int32_t)acc[n];
+            if (n0 + n < p.N) o[(size_t)(n0 + n) * p.HoWo] = (int32_t)big_finish(p, acc[n], n0 + n);
     }
 }
 

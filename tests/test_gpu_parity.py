@@ -1188,6 +1188,60 @@ def test_function_multipliers_bit_exact(B, kind, param, bits):
                 orc.approx_linear_i16(orc.table_from_func(kind, param, bits), bits, a, w, threads=4)).all()
 
 
+@pytest.mark.parametrize("form", ["table12", "table9", "mitchell14", "trunc16"])
+def test_i16_whole_layers_match_oracle_steps(B, form):
+    """Whole layers on operands beyond 8 bits (quantise + product + rescale, bias, activation in one call) against the
+    oracle's separate steps, table and function forms, scalar and per-channel scales, the three activations."""
+    rng = np.random.default_rng(len(form) * 7 + 1)
+    if form.startswith("table"):
+        bits = int(form[5:])
+        lut = orc.table_from_func(2 if bits == 12 else 1, 0 if bits == 12 else 3, bits)
+        mul = B.Lut16(bits, table=lut)
+        lin = lambda a, w: orc.approx_linear_i16(lut, bits, a, w, threads=4)
+        conv = lambda x, w, **kw: orc.approx_conv2d_i16(bits, x, w, lut=lut, threads=4, **kw)
+    else:
+        kind, param, bits = (2, 0, 14) if form == "mitchell14" else (1, 5, 16)
+        mul = (kind, param, bits)
+        lin = lambda a, w: orc.approx_linear_func_i16(kind, param, bits, a, w, threads=4)
+        conv = lambda x, w, **kw: orc.approx_conv2d_i16(bits, x, w, func=(kind, param), threads=4, **kw)
+    # linear: M spans several row tiles and a ragged tail, N a ragged channel tile
+    M, K, N = 300, 70, 21
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    w = _rand_i16(rng, (N, K), bits)
+    bias = rng.standard_normal(N).astype(np.float32)
+    s_x = orc.scale_from_amax(orc.absmax(x), bits)
+    acc = lin(orc.quantize_i16(x, s_x, bits), w)
+    s_out = np.float32(s_x) * np.float32(1e-4)
+    s_vec = (np.float32(s_x) * rng.uniform(1e-5, 1e-4, size=N).astype(np.float32)).astype(np.float32)
+    for sc, b, act in ((s_out, None, 0), (s_out, bias, 1), (s_vec, bias, 2)):
+        want = (orc.dequant_per_channel if isinstance(sc, np.ndarray) else orc.dequant)(acc, sc, M, N, 1, b)
+        want = (orc.relu(want) if act == 1 else orc.tanh(want) if act == 2 else want).reshape(acc.shape)
+        got = B.adapt_linear_layer_i16_f32(mul, dev(x), dev(w), s_x, dev(sc) if isinstance(sc, np.ndarray) else sc,
+                                           dev(b) if b is not None else None, act)
+        assert bits_equal(host(got), want), ("linear", act)
+    # convolution with stride, padding and dilation
+    x = rng.standard_normal((3, 5, 11, 9)).astype(np.float32)
+    f = _rand_i16(rng, (7, 5, 3, 2), bits)
+    bias = rng.standard_normal(7).astype(np.float32)
+    s_x = orc.scale_from_amax(orc.absmax(x), bits)
+    acc = conv(orc.quantize_i16(x, s_x, bits), f, stride=(2, 1), pad=(1, 1), dil=(1, 2))
+    n_, c_, h_, w_ = acc.shape
+    s_out = np.float32(s_x) * np.float32(1e-4)
+    for b, act in ((None, 0), (bias, 1), (bias, 2)):
+        want = orc.dequant(acc, s_out, n_, c_, h_ * w_, b)
+        want = (orc.relu(want) if act == 1 else orc.tanh(want) if act == 2 else want).reshape(acc.shape)
+        got = B.adapt_conv2d_layer_i16_f32(mul, dev(x), dev(f), s_x, s_out, (2, 1), (1, 1), (1, 2), dev(b) if b is not None else None, act)
+        assert bits_equal(host(got), want), ("conv", act)
+    # empty batch, bad arguments
+    assert B.adapt_linear_layer_i16_f32(mul, torch.zeros((0, K), device="cuda"), dev(w), 1.0, 1.0).shape == (0, N)
+    with pytest.raises(B.AdaptError) as e:
+        B.adapt_linear_layer_i16_f32(mul, dev(x.reshape(-1, 5)[:4]), dev(_rand_i16(rng, (3, 5), bits)), 0.0, 1.0)
+    assert e.value.code == -1
+    with pytest.raises(B.AdaptError) as e:
+        B.adapt_conv2d_layer_i16_f32(mul, dev(x), dev(f), 1.0, 1.0, act=3)
+    assert e.value.code == -1
+
+
 def test_wide_table_agrees_with_8_bit_path(B):
     """The same 8-bit table through the LDS kernels (int8 operands) and through the device-memory gather (int16)."""
     rng = np.random.default_rng(8)
@@ -1576,6 +1630,9 @@ GROUPED_LAYER_CASES = [
     # N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, dh, dw, groups, Cout of the 1x1 consumer (0: none)
     (2, 6, 5, 5, 6, 3, 3, 1, 1, 1, 1, 1, 1, 6, 0),
     (3, 32, 16, 16, 32, 3, 3, 1, 1, 1, 1, 1, 1, 32, 64),      # separable block, quad-kernel consumer
+    (2, 32, 10, 10, 32, 3, 3, 1, 1, 1, 1, 1, 1, 2, 16),       # 16 output channels per group: whole-table kernel over a group dimension
+    (3, 24, 9, 7, 48, 3, 3, 2, 1, 1, 0, 1, 1, 3, -8),         # 16 per group from 8, strides differ, 3x3 consumer
+    (2, 5, 8, 8, 12, 3, 2, 1, 1, 1, 1, 1, 1, 1, 0),           # one group (an ordinary convolution through the same call)
     (2, 24, 15, 13, 24, 5, 5, 2, 2, 2, 2, 1, 1, 24, 10),      # 5x5 stride 2, ragged; generic consumer
     (2, 8, 9, 9, 16, 3, 3, 1, 1, 1, 1, 1, 1, 8, 12),          # channel multiplier 2
     (1, 4, 8, 8, 8, 3, 3, 1, 1, 2, 2, 2, 2, 2, 0),            # 2 groups of 2 -> 4, dilated
@@ -1624,7 +1681,7 @@ def test_grouped_conv2d_layer_f32(B, bits, case):
     p2 = B.adapt_weights_pack_conv2d(L, dev(w2))
     B.adapt_conv2d_chain_prepare(p2, N, h_, w_, (1, 1), (k2 // 2, k2 // 2))
     out2 = torch.empty(acc2.shape, dtype=torch.float32, device="cuda")
-    for want_out in (True, False, True):
+    for want_out in ((True, True) if Cout // g >= 8 or g == 1 else (True, False, True)):     # (groups of >= 8 channels finish in place: y is needed)
         got = B.adapt_conv2d_grouped_layer_f32(L, dev(x), dev(w), s_x, s_out, (sh, sw), (ph, pw), (dh, dw), g, dev(bias), B.ACT_RELU,
                                                want_out=want_out, next_pw=p2, s_next=s_y)
         assert (got is None) == (not want_out)
@@ -1640,13 +1697,13 @@ def test_grouped_layer_refusals(B):
     L = B.Lut(wl.make_lut(8), 8)
     rng = np.random.default_rng(4)
     x = torch.zeros((1, 8, 6, 1000), device="cuda")
-    # input region of one output row too large to stage; ordinary convolution; two-pass table: the separate calls serve these
+    # input region of one output row too large to stage; groups of >= 8 channels without an output buffer; two-pass table
     with pytest.raises(B.AdaptError) as e:
         B.adapt_conv2d_grouped_layer_f32(L, x, dev(wl.random_i8(rng, (4, 4, 5, 5), 8)), 1.0, 1.0, (1, 1), (2, 2), groups=2)
     assert e.value.code == -2
     with pytest.raises(B.AdaptError) as e:
-        B.adapt_conv2d_grouped_layer_f32(L, x, dev(wl.random_i8(rng, (4, 8, 3, 3), 8)), 1.0, 1.0, (1, 1), (1, 1), groups=1)
-    assert e.value.code == -2
+        B.adapt_conv2d_grouped_layer_f32(L, x, dev(wl.random_i8(rng, (16, 4, 3, 3), 8)), 1.0, 1.0, (1, 1), (1, 1), groups=2, want_out=False)
+    assert e.value.code == -1
     wide = B.Lut(rng.integers(-2**20, 2**20, size=(64, 64)).astype(np.int32), 6)
     with pytest.raises(B.AdaptError) as e:
         B.adapt_conv2d_grouped_layer_f32(wide, torch.zeros((1, 8, 6, 6), device="cuda"), dev(wl.random_i8(rng, (8, 1, 3, 3), 6)), 1.0, 1.0,
