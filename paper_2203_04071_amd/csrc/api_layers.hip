@@ -366,13 +366,13 @@ template <int R, bool SIGNED, bool REGULAR>
 int launch_lines_fast(const adapt::LinesParams &p, unsigned grid, hipStream_t s) {
     if constexpr (SIGNED) {
         if (p.pair_g) {     // tap pairing exists for single-pass (signed) tables only
-            if (p.bits == 8) adapt::lut_lines_fast_kernel<R, true, REGULAR, true, false, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+            if (p.copy_lines == 256) adapt::lut_lines_fast_kernel<R, true, REGULAR, true, false, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
             else adapt::lut_lines_fast_kernel<R, true, REGULAR, false, false, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
             HIP_TRY(hipGetLastError());
             return ADAPT_OK;
         }
     }
-    if (p.bits == 8) adapt::lut_lines_fast_kernel<R, SIGNED, REGULAR, true, false><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    if (p.copy_lines == 256) adapt::lut_lines_fast_kernel<R, SIGNED, REGULAR, true, false><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
     else adapt::lut_lines_fast_kernel<R, SIGNED, REGULAR, false, false><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
     HIP_TRY(hipGetLastError());
     return ADAPT_OK;
@@ -383,13 +383,13 @@ template <bool SIGNED>
 int launch_lines_xmajor(const adapt::LinesParams &p, unsigned grid, hipStream_t s) {
     if constexpr (SIGNED) {
         if (p.pair_g) {
-            if (p.bits == 8) adapt::lut_lines_fast_kernel<8, true, true, true, true, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+            if (p.copy_lines == 256) adapt::lut_lines_fast_kernel<8, true, true, true, true, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
             else adapt::lut_lines_fast_kernel<8, true, true, false, true, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
             HIP_TRY(hipGetLastError());
             return ADAPT_OK;
         }
     }
-    if (p.bits == 8) adapt::lut_lines_fast_kernel<8, SIGNED, true, true, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
+    if (p.copy_lines == 256) adapt::lut_lines_fast_kernel<8, SIGNED, true, true, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
     else adapt::lut_lines_fast_kernel<8, SIGNED, true, false, true><<<grid, adapt::LINES_THREADS, 0, s>>>(p);
     HIP_TRY(hipGetLastError());
     return ADAPT_OK;
@@ -546,7 +546,8 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     p.d_ntiles = fast_div((uint32_t)p.n_tiles); p.d_mtiles = fast_div((uint32_t)p.m_tiles); p.d_phases = fast_div(1u);
     p.ksplit = pl.ksplit; p.gps = pl.gps; p.ks_out_stride = sums_elsewhere ? (long long)c.out_elems : 0;
     // digit tables: every real lookup of an output lacks the offset (sums wrap in 32 bits like everything else)
-    p.copy_lines = (quad && c.nonneg_in) ? (1 << bits) / 2 : (1 << bits);
+    // (the fast 128-byte-line kernels and the quad kernel copy only the lines that can be selected; the generic kernel copies all)
+    p.copy_lines = c.nonneg_in ? (1 << bits) / 2 : (1 << bits);
     p.corr = quad ? (int)(uint32_t)((unsigned long long)((long long)q.kh * q.kw * q.Cin * (long long)c.quad_c)) : 0;
     // one base offset per lane is enough when the R rows of a lane are equally spaced in xt
     const bool regular = (c.M % R == 0) && (c.HoWo == 1 || c.Wo % R == 0);
@@ -775,7 +776,8 @@ int lines_conv2d(int bits, int storage, const LinesShape &q, uint4 *const dt[2],
     c.phases.resize(1);
     c.out_elems = out_elems; c.out_channels = (size_t)q.N; c.out_inner = (size_t)Ho * Wo;
     if (part_bytes) c.partial = reinterpret_cast<int32_t *>(xt + copy_bytes);
-    if (plan.kernel == LK_QUAD) { c.dt_quad = wh->dtq_dev; c.quad_c = wh->dtq_c; c.nonneg_in = input_ready && wh->chain_in.nonneg; }
+    if (plan.kernel == LK_QUAD) { c.dt_quad = wh->dtq_dev; c.quad_c = wh->dtq_c; }
+    c.nonneg_in = input_ready && wh && wh->chain_in.nonneg;
     bool finished = false;
     int rc = run_lines(bits, storage, q, dt, xt, c, out, s, io, true, nullptr, &finished);
     rc = ws_put(ws, xt, s, rc);
@@ -846,7 +848,8 @@ int lines_conv_transpose2d(int bits, int storage, const LinesShape &q, uint4 *co
     c.out_elems = out_elems; c.out_channels = (size_t)q.N; c.out_inner = (size_t)Ho * Wo;
     if (part_bytes) c.partial = reinterpret_cast<int32_t *>(xt + copy_bytes);
     const bool quad = plan.kernel == LK_QUAD;
-    if (quad) { c.dt_quad = wh->dtq_dev; c.quad_c = wh->dtq_c; c.nonneg_in = input_ready && wh->chain_in.nonneg; }
+    if (quad) { c.dt_quad = wh->dtq_dev; c.quad_c = wh->dtq_c; }
+    c.nonneg_in = input_ready && wh && wh->chain_in.nonneg;
     const bool chained = io && io->chain.buf;
     if ((border || chained) && out_elems < 0x7fffffffull) {     // the product kernel takes the border terms off where it can; its
         if (border) c.zsum = zsum;                              // chained copy needs the true output position of a phase's pixel

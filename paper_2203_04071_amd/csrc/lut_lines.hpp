@@ -121,7 +121,7 @@ struct LinesParams {
     // the divisions every lane (rows -> image, row, column) and every wave (workgroup id -> tiles) starts with, as
     // multiply-and-shift: they were 1 - 2 us of every launch
     FastDiv d_HoWo, d_Wo, d_ntiles, d_mtiles, d_phases;
-    int copy_lines;         // quad kernel: lines of every table that are copied into LDS (all 2^bits, or the first half when
+    int copy_lines;         // quad and fast kernels: lines of every table that are copied into LDS (all 2^bits, or the first half when
                             // the activations are known to be >= 0: their codes then never select the other half)
     int corr;               // quad kernel (digit tables): added to every finished sum, digit_c x real lookups (lut_quad.hpp); else 0
     // Tap pairing (fast kernel, PAIRED): layers with fewer than 32 (padded) channels per tap put pair_g = 32 / Cp taps
@@ -971,7 +971,8 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
 
     // table copy geometry: 8-bit tables take two operations of 64 lanes per wave, smaller tables one
     // operation of table_u4 / 16 lanes per wave
-    const int lanes_act = TWO_OPS ? 64 : (table_u4 >> 4);
+    // (copy_lines: all lines of a table, or the first half when every activation code is known to be >= 0)
+    const int lanes_act = TWO_OPS ? 64 : ((p.copy_lines * 8) >> 4);
     const uint64_t dma_mask = ~0ull >> (64 - lanes_act);       // 1 <= lanes_act <= 64
     const uint32_t dma_voff = (uint32_t)(wave * lanes_act + lane) * 16u;
     const uint32_t lds_tbl = (uint32_t)(uintptr_t)(lds_void_ptr)tbl;
