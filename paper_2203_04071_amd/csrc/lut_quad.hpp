@@ -177,10 +177,12 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
     const int rs = wave * 16 + rl;              // row slot inside the workgroup
     const int wg = (int)p.d_ntiles.div(blockIdx.x);
     const int nt = blockIdx.x - wg * p.n_tiles;
-    const int pk = (int)p.d_mtiles.div((uint32_t)wg);
-    const int mt = wg - pk * p.m_tiles;
-    const int ks = (int)p.d_phases.div((uint32_t)pk);
-    const int ph = pk - ks * p.phases;
+    // The phases of a transposed convolution vary fastest: the stride^2 workgroups that write the interleaved pixels of
+    // the same output lines then run at the same time on the same XCD, and its L2 merges their partial lines.
+    const int rest = (int)p.d_phases.div((uint32_t)wg);
+    const int ph = wg - rest * p.phases;
+    const int ks = (int)p.d_mtiles.div((uint32_t)rest);
+    const int mt = rest - ks * p.m_tiles;
     const int8_t *const xt = p.xt + pick4(p.xt_off, ph);
     const int out_off = pick4(p.out_off, ph);
     int32_t *const outp = p.out + (size_t)ks * p.ks_out_stride;
@@ -198,9 +200,9 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
     const int lanes_act = DOPS > 1 ? 64 : min(64, (int)(copy_bytes >> 8));      // copy_bytes / 16 waves / 16 B
     const uint64_t dma_mask = ~0ull >> (64 - lanes_act);
     const uint32_t dma_voff = (uint32_t)lane * 16u;
-    // (8-bit tables: workgroup number `wg` starts two chunks further on than its predecessor, so that the workgroups
+    // (8-bit tables: workgroup number `rest` (of an n-tile and phase) starts two chunks further on than its predecessor, so that the workgroups
     // that stream one table do not all ask L2 for the same lines at the same moment)
-    const uint32_t dma_rot = DOPS == 4 ? (uint32_t)wg * 2u : 0u;
+    const uint32_t dma_rot = DOPS == 4 ? (uint32_t)rest * 2u : 0u;
     auto dma = [&](int step_, int buf) {
         const int step = step_ < nsteps ? step_ : nsteps - 1;       // past the end: a valid table, never read
         const unsigned char *src = dt + (size_t)(unsigned)step * table_bytes;
@@ -226,13 +228,14 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
     // the 128-byte lines of the table QUAD_PF_DIST steps ahead with one plain load per wave (a few active addresses,
     // result never used): the copy operations one step later then hit in L2.
     const int pf_span = (p.n_tiles < 8 && 8 % p.n_tiles == 0) ? 8 / p.n_tiles : 1;
-    const int pf_peers = max(1, min(32, (int)(gridDim.x / (unsigned)p.n_tiles) / pf_span));
+    // (`rest` numbers the workgroups of one n-tile and phase; 32 workgroups of an XCD run at a time, the phases among them)
+    const int pf_peers = max(1, min(32 / p.phases, (int)(gridDim.x / (unsigned)(p.n_tiles * p.phases)) / pf_span));
     const int pf_share = 1 << (31 - __builtin_clz((unsigned)pf_peers));         // a power of two
     const int pf_lines = (int)(copy_bytes >> 7);
     const int pf_per_wg = (pf_lines + pf_share - 1) / pf_share;
     const int pf_per_wave = (pf_per_wg + 15) >> 4;                              // <= 32 (512 lines, one workgroup)
     const uint32_t pf_voff =
-        128u * (uint32_t)min(((wg / pf_span) & (pf_share - 1)) * pf_per_wg + wave * pf_per_wave + min(lane, pf_per_wave - 1), pf_lines - 1);
+        128u * (uint32_t)min(((rest / pf_span) & (pf_share - 1)) * pf_per_wg + wave * pf_per_wave + min(lane, pf_per_wave - 1), pf_lines - 1);
     uint32_t pf_sink = 0;
     auto prefetch = [&](int step_) {
         const int step = step_ < nsteps ? step_ : nsteps - 1;
