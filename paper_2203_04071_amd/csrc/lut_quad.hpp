@@ -177,10 +177,18 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
     const int rs = wave * 16 + rl;              // row slot inside the workgroup
     const int wg = (int)p.d_ntiles.div(blockIdx.x);
     const int nt = blockIdx.x - wg * p.n_tiles;
-    // The phases of a transposed convolution vary fastest: the stride^2 workgroups that write the interleaved pixels of
-    // the same output lines then run at the same time on the same XCD, and its L2 merges their partial lines.
-    const int rest = (int)p.d_phases.div((uint32_t)wg);
-    const int ph = wg - rest * p.phases;
+    // Consecutive workgroup numbers go to consecutive XCDs.  With 8 n-tiles (or a multiple) an n-tile stays on one XCD;
+    // with 4 / 2 / 1 n-tiles every 2nd / 4th / 8th workgroup `wg` of an n-tile shares its XCD (xcd_span).  The phases of
+    // a transposed convolution vary fastest AMONG THE WORKGROUPS OF ONE XCD: the stride^2 workgroups that write the
+    // interleaved pixels of the same output lines then run at about the same time behind the same L2, which merges
+    // their partial lines.  `rest` numbers the workgroups of one n-tile and phase (row tile and slice of the inner
+    // dimension).
+    int xcd_span = (p.n_tiles < 8 && 8 % p.n_tiles == 0) ? 8 / p.n_tiles : 1;
+    if ((p.m_tiles * p.ksplit) % xcd_span) xcd_span = 1;
+    const int wx = wg & (xcd_span - 1), wy = wg / xcd_span;
+    const int wz = (int)p.d_phases.div((uint32_t)wy);
+    const int ph = wy - wz * p.phases;
+    const int rest = wz * xcd_span + wx;
     const int ks = (int)p.d_mtiles.div((uint32_t)rest);
     const int mt = rest - ks * p.m_tiles;
     const int8_t *const xt = p.xt + pick4(p.xt_off, ph);
@@ -227,7 +235,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
     // first copy of every step would wait for device memory.  So each of up to 32 such workgroups touches its share of
     // the 128-byte lines of the table QUAD_PF_DIST steps ahead with one plain load per wave (a few active addresses,
     // result never used): the copy operations one step later then hit in L2.
-    const int pf_span = (p.n_tiles < 8 && 8 % p.n_tiles == 0) ? 8 / p.n_tiles : 1;
+    const int pf_span = (p.n_tiles < 8 && 8 % p.n_tiles == 0) ? 8 / p.n_tiles : 1;     // (as xcd_span, without its fallback)
     // (`rest` numbers the workgroups of one n-tile and phase; 32 workgroups of an XCD run at a time, the phases among them)
     const int pf_peers = max(1, min(32 / p.phases, (int)(gridDim.x / (unsigned)(p.n_tiles * p.phases)) / pf_span));
     const int pf_share = 1 << (31 - __builtin_clz((unsigned)pf_peers));         // a power of two
