@@ -250,7 +250,11 @@ int adapt_conv2d_grouped_layer_f32(const adapt_lut *lut, const float *x_dev, con
  * adapt_conv2d_layer_chain_f32 is adapt_conv2d_layer_f32 with two additions:
  *   x_dev == NULL: the input copy is already in the prepared workspace of `h` (written by the layer before);
  *   next != NULL : y is ALSO written into the prepared workspace of `next` as its input copy, quantised with
- *                  s_next exactly as adapt_quantize_f32 would quantise y_dev (the output y_dev is still written).
+ *                  s_next exactly as adapt_quantize_f32 would quantise y_dev.  y_dev is written too, unless it is NULL:
+ *                  a caller that wants nothing but next's copy may pass y_dev == NULL with next != NULL.  That works
+ *                  where the product kernel itself finishes the sums and writes the copy; a shape whose sums are
+ *                  finished in a separate pass over the output (inner dimension split over workgroups, two-pass
+ *                  tables) returns ADAPT_ERR_UNSUPPORTED with next's copy untouched and needs the buffer.
  * `next` must have been prepared for N images of this layer's output size and have as many input channels as this
  * layer has output channels, and must be another handle than `w`; otherwise ADAPT_ERR_INVALID_ARGUMENT.  An ordinary call on a prepared handle with
  * another geometry ends its prepared state.  Results are identical to the unchained calls. */
@@ -346,8 +350,9 @@ int adapt_rnn_cell_f32(const int32_t *acc_ih_dev, const int32_t *acc_hh_dev, flo
  * one input pixel) can be prepared: ADAPT_ERR_UNSUPPORTED otherwise.
  * adapt_conv_transpose2d_layer_chain_f32: adapt_conv_transpose2d_layer_f32 with x_dev == NULL allowed (prepared handle)
  * and, when next != NULL (a prepared conv2d or transposed-conv2d handle whose input is this layer's output), the output
- * also written as next's quantised input copy with scale s_next.  y_dev is always written.  Every geometry is accepted
- * as a producer. */
+ * also written as next's quantised input copy with scale s_next.  y_dev may be NULL when next != NULL, under the same
+ * condition as for adapt_conv2d_layer_chain_f32 (ADAPT_ERR_UNSUPPORTED otherwise).  Every geometry is accepted as a
+ * producer. */
 int adapt_conv_transpose2d_chain_prepare(const adapt_weights *h, int N, int H, int W, int pad, void *stream);
 int adapt_conv_transpose2d_layer_chain_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W,
                                            int pad, float s_x, float s_out, const float *s_out_vec_dev,

@@ -621,7 +621,8 @@ def adapt_conv2d_layer_chain_f32(pw: PackedWeights, x, s_x, s_out, out, stride=(
                                  act=ACT_NONE, residual=None, next_pw: PackedWeights = None, s_next: float = 1.0, in_shape=None,
                                  stream=None):
     """x None: the input copy is already in pw's prepared workspace (in_shape = (N, H, W) then); next_pw: also write the
-    output as next_pw's input copy, quantised with s_next.  `out` (fp32 [N][Cout][Ho][Wo]) is required."""
+    output as next_pw's input copy, quantised with s_next.  `out` (fp32 [N][Cout][Ho][Wo]) may be None when next_pw is given and
+    only that copy is wanted; shapes that finish their sums in a separate pass then raise AdaptError with code -2."""
     if x is not None:
         N, Cin, H, W = x.shape
     else:
@@ -673,7 +674,8 @@ def adapt_conv_transpose2d_chain_prepare(pw: PackedWeights, N, H, W, pad=0, stre
 def adapt_conv_transpose2d_layer_chain_f32(pw: PackedWeights, x, s_x, s_out, out, pad=0, bias=None, act=ACT_NONE,
                                            next_pw: PackedWeights = None, s_next: float = 1.0, in_shape=None, stream=None):
     """x None: the input copy is already in pw's prepared workspace (in_shape = (N, H, W) then); next_pw: also write the
-    output as next_pw's input copy, quantised with s_next.  `out` (fp32 [N][Cout][Ho][Wo]) is required."""
+    output as next_pw's input copy, quantised with s_next.  `out` (fp32 [N][Cout][Ho][Wo]) may be None when next_pw is given and
+    only that copy is wanted; shapes that finish their sums in a separate pass then raise AdaptError with code -2."""
     if x is not None:
         N, Cin, H, W = x.shape
     else:

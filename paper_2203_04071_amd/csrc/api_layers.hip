@@ -564,6 +564,11 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     const bool chain_in_kernel = fuse_in_kernel && io->chain.buf;
     const bool extra = quad && (border_in_kernel || (fuse_in_kernel && io->act == 2) || chain_in_kernel);
     p.chain = chain_in_kernel ? io->chain : adapt::ChainOut{};
+    // a caller that only wants the next layer's copy passes no output buffer; that works where the product kernel itself
+    // finishes the sums and writes the copy (no partial sums, no separate finishing pass, residual aside)
+    if (!out && !chain_in_kernel)
+        return fail(ADAPT_ERR_UNSUPPORTED, "this layer shape finishes its sums in a separate pass over the output: y_dev is needed");
+    p.no_out = out ? 0 : 1;
     p.zsum = border_in_kernel ? c.zsum : nullptr;
     p.cv_s = fast_div((uint32_t)c.cv_s);
     p.cv_Ho = c.cv_Ho; p.cv_Wo = c.cv_Wo; p.cv_H = c.cv_H; p.cv_W = c.cv_W; p.cv_kh = c.cv_kh; p.cv_kw = c.cv_kw;
@@ -1369,9 +1374,10 @@ int adapt_approx_conv2d_packed(const adapt_weights *h, const int8_t *x_dev, int3
 
 /* ------------------------------------------------------------------ whole layers, fp32 in and out */
 
+// y_optional: the caller chains into a next layer and may want nothing but that layer's input copy
 static int layer_io(LayerIO *io, const adapt_weights *h, const float *x_dev, const float *y_dev, float s_x, float s_out,
-                    const float *s_out_vec_dev, const float *bias_dev, int act, const char *who) {
-    if (!x_dev || !y_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
+                    const float *s_out_vec_dev, const float *bias_dev, int act, const char *who, bool y_optional = false) {
+    if (!x_dev || (!y_dev && !y_optional)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: NULL pointer", who);
     if (!(s_x > 0.0f)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: s_x must be > 0", who);
     if (act < 0 || act > 2) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: act=%d not in {0, 1, 2}", who, act);
     io->xf = x_dev; io->s_x = s_x; io->Q = (float)((1 << (h->bits - 1)) - 1);
@@ -1451,11 +1457,12 @@ static int conv2d_layer(const adapt_weights *h, const float *x_dev, float *y_dev
             return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: x_dev is NULL but the handle was not prepared for this geometry", who);
     }
     LayerIO io;
-    if ((rc = layer_io(&io, h, input_ready ? reinterpret_cast<const float *>(y_dev) : x_dev, y_dev, s_x, s_out, s_out_vec_dev, bias_dev, act, who)))
+    if ((rc = layer_io(&io, h, input_ready ? reinterpret_cast<const float *>(h) : x_dev, y_dev, s_x, s_out, s_out_vec_dev, bias_dev, act, who,
+                       next != nullptr)))
         return rc;
     if (input_ready) io.xf = nullptr;
     io.resid = residual_dev;
-    if (residual_dev == y_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: residual_dev must not alias y_dev", who);
+    if (residual_dev && residual_dev == y_dev) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: residual_dev must not alias y_dev", who);
     if (next) {
         if ((rc = check_weights(next, 1, who))) return rc;
         if (next == h) return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: a layer cannot chain into itself (one workspace per handle)", who);
@@ -1680,7 +1687,8 @@ int adapt_conv_transpose2d_layer_chain_f32(const adapt_weights *h, const float *
             return fail(ADAPT_ERR_INVALID_ARGUMENT, "%s: x_dev is NULL but the handle was not prepared for this geometry", who);
     }
     LayerIO io;
-    if ((rc = layer_io(&io, h, input_ready ? reinterpret_cast<const float *>(y_dev) : x_dev, y_dev, s_x, s_out, s_out_vec_dev, bias_dev, act, who)))
+    if ((rc = layer_io(&io, h, input_ready ? reinterpret_cast<const float *>(h) : x_dev, y_dev, s_x, s_out, s_out_vec_dev, bias_dev, act, who,
+                       next != nullptr)))
         return rc;
     if (input_ready) io.xf = nullptr;
     if (next) {
@@ -1703,6 +1711,7 @@ int adapt_conv_transpose2d_layer_chain_f32(const adapt_weights *h, const float *
     if (input_ready || phase_form)
         return lines_conv_transpose2d(h->bits, h->storage, q, h->dt_dev, h->zsum_dev, nullptr, out, N, H, W, h->kh, h->kw, h->stride, pad, s,
                                       &h->ws, &io, h, input_ready);
+    if (!y_dev) return fail(ADAPT_ERR_UNSUPPORTED, "%s: this geometry finishes its sums in a separate pass over the output: y_dev is needed", who);
     int8_t *q8 = nullptr;
     if ((rc = quantize_into_ws(h, io, (size_t)N * h->Cin * H * W, s, &q8))) return rc;
     return convt_rows(h->lut, q8, h->w8_dev, out, N, h->Cin, H, W, h->N, h->kh, h->kw, h->stride, pad, s, h, &io);

@@ -121,6 +121,7 @@ struct LinesParams {
     // the divisions every lane (rows -> image, row, column) and every wave (workgroup id -> tiles) starts with, as
     // multiply-and-shift: they were 1 - 2 us of every launch
     FastDiv d_HoWo, d_Wo, d_ntiles, d_mtiles, d_phases;
+    int no_out;             // 1: only the chained copy is wanted, the finished sums are not stored (out is then never dereferenced)
     int copy_lines;         // quad and fast kernels: lines of every table that are copied into LDS (all 2^bits, or the first half when
                             // the activations are known to be >= 0: their codes then never select the other half)
     int corr;               // quad kernel (digit tables): added to every finished sum, digit_c x real lookups (lut_quad.hpp); else 0
@@ -850,7 +851,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_kernel(const LinesPar
             int32_t *q = p.out + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
             if (p.shift < 0) {
                 const uint32_t f = finish_sum(p, w[i][t], n, (size_t)(q - p.out));
-                *q = (int32_t)f;
+                if (!p.no_out) *q = (int32_t)f;
                 if (p.chain.buf) p.chain.put(img, n, a, b, __uint_as_float(f));
             } else {
                 *q = (int32_t)((uint32_t)*q + (w[i][t] << p.shift));
@@ -1240,7 +1241,9 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
                     for (int i = 0; i < 4; ++i) p.chain.put(img, n, a0, b0 + i, __uint_as_float(f[i]));
                 }
             }
-            if (p.shift < 0 && sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
+            if (p.no_out) {
+                // only the chained copy is wanted
+            } else if (p.shift < 0 && sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
                 *reinterpret_cast<uint4 *>(q0) = make_uint4(f[0], f[1], f[2], f[3]);
             } else {
 #pragma unroll
@@ -1275,7 +1278,7 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_lines_fast_kernel(const Lin
                 int32_t *q = outp + ((size_t)img * p.N + n) * p.out_plane + out_off + a * p.out_sy + b * p.out_sx;
                 if (p.shift < 0) {
                     const uint32_t f = finish_sum(p, w[i][t], n, (size_t)(q - outp));
-                    *q = (int32_t)f;
+                    if (!p.no_out) *q = (int32_t)f;
                     if (p.chain.buf) p.chain.put(img, n, a, b, __uint_as_float(f));
                 } else {
                     *q = (int32_t)((uint32_t)*q + (w[i][t] << p.shift));

@@ -459,7 +459,9 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
                     else p.chain.put(img, n, a0, b0 + i, __uint_as_float(f[i]));
                 }
             }
-            if (sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
+            if (EXTRA && p.no_out) {
+                // only the chained copy is wanted
+            } else if (sx == 1 && (reinterpret_cast<uintptr_t>(q0) & 15u) == 0) {
                 *reinterpret_cast<uint4 *>(q0) = make_uint4(f[0], f[1], f[2], f[3]);
             } else {
 #pragma unroll

@@ -64,6 +64,13 @@ class Captured:
         return self.out
 
 
+class _ShapeOnly:
+    """Stands for the fp32 output of a chained layer that was not written: the next layer needs its shape only."""
+
+    def __init__(self, shape, device):
+        self.shape, self.device = tuple(shape), device
+
+
 class ResNet20:
     def __init__(self, cfg, device="cuda"):
         self.bits = cfg["bits"]
@@ -79,6 +86,7 @@ class ResNet20:
         self.macs = None
         self.chain = True           # frozen scales: every layer also writes the next layer's quantised input copy
         self._prepared = None       # input shape the chained buffers were prepared for
+        self._needs_out = set()     # layers that need their fp32 output buffer even when nobody reads it
 
     def _prepare_chain(self, x):
         """Fix the place and layout of every convolution's input copy (all but the first receive it from the layer before)."""
@@ -89,7 +97,7 @@ class ResNet20:
             h, w = (h + 2 - 3) // st + 1, (w + 2 - 3) // st + 1
         self._prepared = tuple(x.shape)
 
-    def _conv(self, i, x, used, keep, relu=False, residual=None):
+    def _conv(self, i, x, used, keep, relu=False, residual=None, want_out=True):
         """conv (+ ReLU).  Once the scales are frozen and nobody asks for the integer sums, the layer runs as one
         fused call (quantise while laying out the input, rescale + ReLU inside the product kernel)."""
         bits = self.bits
@@ -102,12 +110,26 @@ class ResNet20:
                 # this layer's scale, from its epilogue); x is only needed for its shape
                 n, _, h, w = x.shape
                 ho, wo = (h + 2 - 3) // st + 1, (w + 2 - 3) // st + 1
-                out = torch.empty((n, self.plan[i][1], ho, wo), dtype=torch.float32, device=x.device)
+                shape = (n, self.plan[i][1], ho, wo)
                 last = i + 1 == len(self.plan)
-                return B.adapt_conv2d_layer_chain_f32(self.pws[i], x if i == 0 else None, s_x, _f(s_x) * _f(self.qws[i][1]), out, (st, st),
-                                                      (1, 1), act=B.ACT_RELU if relu else B.ACT_NONE, residual=residual,
-                                                      next_pw=None if last else self.pws[i + 1],
-                                                      s_next=1.0 if last else self.scales[i + 1], in_shape=(n, h, w))
+                # a layer whose fp32 output nobody reads (only the next layer's copy is wanted) passes no output buffer,
+                # unless its shape finishes the sums in a separate pass (found out on the first pass, remembered)
+                skip = (not want_out) and (not last) and i not in self._needs_out
+                for attempt in (0, 1):
+                    out = None if skip else torch.empty(shape, dtype=torch.float32, device=x.device)
+                    try:
+                        B.adapt_conv2d_layer_chain_f32(self.pws[i], x if i == 0 else None, s_x, _f(s_x) * _f(self.qws[i][1]), out, (st, st),
+                                                       (1, 1), act=B.ACT_RELU if relu else B.ACT_NONE, residual=residual,
+                                                       next_pw=None if last else self.pws[i + 1],
+                                                       s_next=1.0 if last else self.scales[i + 1], in_shape=(n, h, w))
+                    except B.AdaptError as e:
+                        if not (skip and e.code == -2):
+                            raise
+                        self._needs_out.add(i)
+                        skip = False
+                        continue
+                    break
+                return out if out is not None else _ShapeOnly(shape, x.device)
             return B.adapt_conv2d_layer_f32(self.pws[i], x, s_x, _f(s_x) * _f(self.qws[i][1]), (st, st), (1, 1),
                                             act=B.ACT_RELU if relu else B.ACT_NONE, residual=residual)
         s_x = calibrated_scale(x, bits) if self.scales is None else self.scales[i]
@@ -130,7 +152,7 @@ class ResNet20:
         i = 1
         while i < len(self.plan):
             cin, cout, stride = self.plan[i]
-            y = self._conv(i, x, used, keep, relu=True)
+            y = self._conv(i, x, used, keep, relu=True, want_out=False)     # (read only by the next layer, through its copy)
             sc = x if (stride == 1 and cin == cout) else B.adapt_shortcut_a_f32(x, cout)
             x = self._conv(i + 1, y, used, keep, relu=True, residual=sc)      # residual add + ReLU in the layer's epilogue
             i += 2
@@ -344,16 +366,25 @@ class DCGAN:
                     raise
                 self.chain = False
                 return None
-            self._outs = [torch.empty(shapes[i + 1], dtype=torch.float32, device=z.device) for i in range(nl)]
+            # only the last layer's fp32 output is read; the others get a buffer only if their shape needs one
+            self._outs = [None] * (nl - 1) + [torch.empty(shapes[nl], dtype=torch.float32, device=z.device)]
             self._chain_shape = shapes[0]
         x = z
         for i, (cin, cout, s, p) in enumerate(self.plan):
             s_x = self.scales[i]
             nxt = self.pws[i + 1] if i + 1 < nl else None
-            B.adapt_conv_transpose2d_layer_chain_f32(self.pws[i], x if i == 0 else None, s_x, _f(s_x) * _f(self.qws[i][1]), self._outs[i], p,
-                                                     act=B.ACT_TANH if i == nl - 1 else B.ACT_RELU, next_pw=nxt,
-                                                     s_next=self.scales[i + 1] if nxt is not None else 1.0,
-                                                     in_shape=(n, shapes[i][2], shapes[i][3]))
+            for attempt in (0, 1):
+                try:
+                    B.adapt_conv_transpose2d_layer_chain_f32(self.pws[i], x if i == 0 else None, s_x, _f(s_x) * _f(self.qws[i][1]),
+                                                             self._outs[i], p, act=B.ACT_TANH if i == nl - 1 else B.ACT_RELU, next_pw=nxt,
+                                                             s_next=self.scales[i + 1] if nxt is not None else 1.0,
+                                                             in_shape=(n, shapes[i][2], shapes[i][3]))
+                except B.AdaptError as e:
+                    if not (self._outs[i] is None and e.code == -2):
+                        raise
+                    self._outs[i] = torch.empty(shapes[i + 1], dtype=torch.float32, device=z.device)
+                    continue
+                break
         return self._outs[-1]
 
     def forward(self, z, keep=None):

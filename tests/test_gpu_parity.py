@@ -1591,6 +1591,29 @@ def test_chained_conv_layers_match_unchained_and_oracle(B, case):
                                        in_shape=(N,) + shapes[2][2:])
         for i in range(3):
             assert bits_equal(host(outs[i]), acts[i + 1]), (rep, i)
+    # the first two layers without their fp32 outputs (only the next layer's copy is wanted): the last layer's output must
+    # not change; a shape that finishes its sums in a separate pass refuses (code -2) and leaves everything as it was
+    outs[2].zero_()
+    skipped = []
+    for i, (xin, st, shp) in enumerate(((dev(x), 1, None), (None, s2, (N,) + shapes[1][2:]))):
+        kw = dict(bias=dev(bs[i]), act=B.ACT_RELU, next_pw=pws[i + 1], s_next=scales[i + 1])
+        if shp is not None:
+            kw["in_shape"] = shp
+        try:
+            B.adapt_conv2d_layer_chain_f32(pws[i], xin, scales[i], np.float32(scales[i]) * np.float32(0.01), None, (st, st), (1, 1), **kw)
+            skipped.append(i)
+        except B.AdaptError as e:
+            assert e.code == -2, e
+            B.adapt_conv2d_layer_chain_f32(pws[i], xin, scales[i], np.float32(scales[i]) * np.float32(0.01), outs[i], (st, st), (1, 1), **kw)
+    B.adapt_conv2d_layer_chain_f32(pws[2], None, scales[2], np.float32(scales[2]) * np.float32(0.01), outs[2], (1, 1), (1, 1),
+                                   bias=dev(bs[2]), act=B.ACT_RELU, residual=outs[1] if chans[2] == chans[1] else None,
+                                   in_shape=(N,) + shapes[2][2:])
+    assert bits_equal(host(outs[2]), acts[3]), skipped
+    if case[:4] == (32, 64, 32, 32):
+        assert skipped == [0, 1]        # the layer of configuration 2 writes the copy from the product kernel
+    with pytest.raises(B.AdaptError) as e:      # no output and no next layer: nothing to do
+        B.adapt_conv2d_layer_chain_f32(pws[2], None, scales[2], 1.0, None, (1, 1), (1, 1), in_shape=(N,) + shapes[2][2:])
+    assert e.value.code == -1
 
 
 @pytest.mark.parametrize("bits", [8, 7, 5])
