@@ -160,6 +160,28 @@ __device__ __forceinline__ uint32_t convt_border_terms(const LinesParams &p, int
     return extra;
 }
 
+// The same for the four pixels (oy, ox + i * stride), i = 0 .. 3, of one phase: they share the row's taps and the column
+// residue, so every zero sum is loaded once.
+__device__ __forceinline__ void convt_border_terms4(const LinesParams &p, int co, int oy, int ox, uint32_t (&extra)[4]) {
+    const int st = (int)p.cv_s.d;
+    const int qy = (int)p.cv_s.div((uint32_t)(oy + p.cv_pad)), ry = oy + p.cv_pad - qy * st;
+    const int qx = (int)p.cv_s.div((uint32_t)(ox + p.cv_pad)), rx = ox + p.cv_pad - qx * st;
+    const int32_t *z = p.zsum + (size_t)co * p.cv_kh * p.cv_kw;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) extra[i] = 0;
+    for (int m = 0; m * st + ry < p.cv_kh; ++m) {
+        const bool yin = qy - m >= 0 && qy - m < p.cv_H;
+        for (int nn = 0; nn * st + rx < p.cv_kw; ++nn) {
+            const int x0 = qx - nn;             // input column of pixel 0; pixel i has x0 + i
+            if (yin && x0 >= 0 && x0 + 3 < p.cv_W) continue;
+            const uint32_t zz = (uint32_t)z[(ry + st * m) * p.cv_kw + (rx + st * nn)];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (!(yin && (unsigned)(x0 + i) < (unsigned)p.cv_W)) extra[i] += zz;
+        }
+    }
+}
+
 // EXTRA: the instantiation also knows tanh; the plain one does not (eight inlined copies of that code in an epilogue
 // cost the ordinary layers about a microsecond per launch)
 template <bool EXTRA = false>

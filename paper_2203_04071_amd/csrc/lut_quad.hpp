@@ -443,9 +443,11 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
             uint32_t v[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) v[i] = w[4 * run + i][cc];
-            if (EXTRA && near_border) {
+            if (EXTRA && near_border) {     // (out_sx is the stride there)
+                uint32_t extra[4];
+                convt_border_terms4(p, n, oy, ox, extra);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] -= convt_border_terms(p, n, oy, ox + i * p.out_sx);
+                for (int i = 0; i < 4; ++i) v[i] -= extra[i];
             }
             int32_t *q0 = outp + ((size_t)img * p.N + n) * p.out_plane + out_off + a0 * p.out_sy + b0 * p.out_sx;
             uint32_t f[4];
