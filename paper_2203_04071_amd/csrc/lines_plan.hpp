@@ -61,10 +61,11 @@ inline long long quad_cost(int R, int M, int tiles, int steps, int bits, int cu)
 }
 
 // The quad kernel takes a product when its tables exist, the window moves one pixel at a time, the inner dimension has
-// at least QUAD_MIN_STEPS steps and some admissible R gives at least three quarters of the compute units a workgroup
-// (layers below that - few steps, or so few rows that the inner dimension has to be split over workgroups - measured
-// the same or faster on the 128-byte-line kernels inside a network, where a layer's tables arrive cold).
-constexpr int QUAD_MIN_STEPS = 16;
+// at least QUAD_MIN_STEPS steps and some admissible R gives at least three quarters of the compute units a workgroup.
+// Measured inside networks (tables arrive cold): 9-step 3 x 3 layers of 16 channels and an 8-step 1 x 1 layer of 128
+// channels are 10 - 20 % faster on it than on the 128-byte-line kernels; layers that would cover only half the compute
+// units (or need the inner dimension split over workgroups) are not.
+constexpr int QUAD_MIN_STEPS = 4;
 
 inline LinesPlan plan_lines(const PlanIn &in) {
     const int M = in.M, cu = in.cu;

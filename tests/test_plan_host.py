@@ -21,9 +21,12 @@ def test_headline_layer_runs_on_the_quad_kernel_unsplit(plan):
 def test_resnet20_layers(plan):
     # first layer: 3 channels (padded to 8): no quad tables; x-major copy, 128-byte lines, paired taps
     assert plan(1, 8, 0, 16, 3, 3, 3, 1, 128 * 32 * 32, 32, 1)[:3] == (XMAJOR, 1024, 1)
-    # stage 1: 16 channels, 9 steps of 16: too few steps for the quad kernel
-    assert plan(1, 8, 0, 16, 16, 3, 3, 1, 128 * 32 * 32, 32, 1)[:3] == (XMAJOR, 1024, 1)
-    # stage 2: 32 channels, 32768 rows: 4 rows per lane on the 128-byte-line kernel
+    # stage 1: 16 channels, 9 steps of 16, 131072 rows x 2 channel tiles: quad kernel, 4 rows per row slot, 256 workgroups
+    assert plan(1, 8, 0, 16, 16, 3, 3, 1, 128 * 32 * 32, 32, 1) == (QUAD, 1024, 1, 9, 256)
+    # a 1x1 layer of 32 channels has 2 steps: below the quad kernel's minimum of 4
+    assert plan(1, 8, 0, 16, 32, 1, 1, 1, 128 * 32 * 32, 32, 1)[0] != QUAD
+    # stage 2: 32 channels, 32768 rows: the quad kernel would cover half the compute units; 4 rows per lane on the
+    # 128-byte-line kernel
     assert plan(1, 8, 0, 32, 32, 3, 3, 1, 128 * 16 * 16, 16, 1)[:3] == (FAST, 512, 1)
     # stage 3: 64 channels, 8192 rows: inner dimension split over 4 workgroups
     k, rows, ksplit, steps, wgs = plan(1, 8, 0, 64, 64, 3, 3, 1, 128 * 8 * 8, 8, 1)
