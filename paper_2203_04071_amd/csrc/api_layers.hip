@@ -1474,11 +1474,13 @@ static int conv2d_layer(const adapt_weights *h, const float *x_dev, float *y_dev
         io.chain.xmajor = ci.xmajor; io.chain.Hp = ci.H + 2 * ci.ph; io.chain.Wp = ci.W + 2 * ci.pw; io.chain.Cp = next->Cp;
         io.chain.ph = ci.ph; io.chain.pw = ci.pw;
         io.chain.scale = s_next; io.chain.Q = (float)((1 << (next->bits - 1)) - 1); io.chain.mask = (1u << next->bits) - 1u;
-        next->chain_in.nonneg = act == 1;
         io.chain_wo = (int)g.Wo;
     }
-    return lines_conv2d(h->bits, h->storage, shape_of(h), h->dt_dev, nullptr, reinterpret_cast<int32_t *>(y_dev), N, H, W, (int)g.Ho,
-                        (int)g.Wo, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream, &h->ws, &io, h, input_ready);
+    rc = lines_conv2d(h->bits, h->storage, shape_of(h), h->dt_dev, nullptr, reinterpret_cast<int32_t *>(y_dev), N, H, W, (int)g.Ho,
+                      (int)g.Wo, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, (hipStream_t)stream, &h->ws, &io, h, input_ready);
+    // (only a call that has written next's copy may say what the copy holds)
+    if (rc == ADAPT_OK && next) next->chain_in.nonneg = act == 1;
+    return rc;
 }
 
 int adapt_conv2d_layer_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W, int stride_h, int stride_w,
@@ -1562,7 +1564,6 @@ int adapt_conv2d_grouped_layer_f32(const adapt_lut *lut, const float *x_dev, con
         io.chain.xmajor = ci.xmajor; io.chain.Hp = ci.H + 2 * ci.ph; io.chain.Wp = ci.W + 2 * ci.pw; io.chain.Cp = next->Cp;
         io.chain.ph = ci.ph; io.chain.pw = ci.pw;
         io.chain.scale = s_next; io.chain.Q = (float)((1 << (next->bits - 1)) - 1); io.chain.mask = (1u << next->bits) - 1u;
-        next->chain_in.nonneg = act == 1;
         io.chain_wo = (int)Wo;
     }
     if (wide_groups) {
@@ -1586,10 +1587,12 @@ int adapt_conv2d_grouped_layer_f32(const adapt_lut *lut, const float *x_dev, con
         }
         hipError_t fe = hipFreeAsync(q8, s);
         if (rc == ADAPT_OK && fe != hipSuccess) rc = fail(ADAPT_ERR_HIP, "hipFreeAsync: %s", hipGetErrorString(fe));
-        return rc;
+    } else {
+        rc = run_grouped(lut, nullptr, w_dev, reinterpret_cast<int32_t *>(y_dev), N, Cin, H, W, Cout, (int)Ho, (int)Wo, kh, kw, stride_h,
+                         stride_w, pad_h, pad_w, dil_h, dil_w, groups, (hipStream_t)stream, &io);
     }
-    return run_grouped(lut, nullptr, w_dev, reinterpret_cast<int32_t *>(y_dev), N, Cin, H, W, Cout, (int)Ho, (int)Wo, kh, kw, stride_h,
-                       stride_w, pad_h, pad_w, dil_h, dil_w, groups, (hipStream_t)stream, &io);
+    if (rc == ADAPT_OK && next) next->chain_in.nonneg = act == 1;
+    return rc;
 }
 
 int adapt_conv_transpose2d_layer_f32(const adapt_weights *h, const float *x_dev, float *y_dev, int N, int H, int W, int pad, float s_x,
@@ -1703,18 +1706,21 @@ int adapt_conv_transpose2d_layer_chain_f32(const adapt_weights *h, const float *
         io.chain.xmajor = ci.xmajor; io.chain.Hp = ci.H + 2 * ci.ph; io.chain.Wp = ci.W + 2 * ci.pw; io.chain.Cp = next->Cp;
         io.chain.ph = ci.ph; io.chain.pw = ci.pw;
         io.chain.scale = s_next; io.chain.Q = (float)((1 << (next->bits - 1)) - 1); io.chain.mask = (1u << next->bits) - 1u;
-        next->chain_in.nonneg = act == 1;
         io.chain_wo = (int)Wo;
     }
     hipStream_t s = (hipStream_t)stream;
     int32_t *out = reinterpret_cast<int32_t *>(y_dev);
-    if (input_ready || phase_form)
-        return lines_conv_transpose2d(h->bits, h->storage, q, h->dt_dev, h->zsum_dev, nullptr, out, N, H, W, h->kh, h->kw, h->stride, pad, s,
-                                      &h->ws, &io, h, input_ready);
-    if (!y_dev) return fail(ADAPT_ERR_UNSUPPORTED, "%s: this geometry finishes its sums in a separate pass over the output: y_dev is needed", who);
-    int8_t *q8 = nullptr;
-    if ((rc = quantize_into_ws(h, io, (size_t)N * h->Cin * H * W, s, &q8))) return rc;
-    return convt_rows(h->lut, q8, h->w8_dev, out, N, h->Cin, H, W, h->N, h->kh, h->kw, h->stride, pad, s, h, &io);
+    if (input_ready || phase_form) {
+        rc = lines_conv_transpose2d(h->bits, h->storage, q, h->dt_dev, h->zsum_dev, nullptr, out, N, H, W, h->kh, h->kw, h->stride, pad, s,
+                                    &h->ws, &io, h, input_ready);
+    } else {
+        if (!y_dev) return fail(ADAPT_ERR_UNSUPPORTED, "%s: this geometry finishes its sums in a separate pass over the output: y_dev is needed", who);
+        int8_t *q8 = nullptr;
+        if ((rc = quantize_into_ws(h, io, (size_t)N * h->Cin * H * W, s, &q8))) return rc;
+        rc = convt_rows(h->lut, q8, h->w8_dev, out, N, h->Cin, H, W, h->N, h->kh, h->kw, h->stride, pad, s, h, &io);
+    }
+    if (rc == ADAPT_OK && next) next->chain_in.nonneg = act == 1;
+    return rc;
 }
 
 /* ------------------------------------------------------------------ LSTM time step in one kernel */
