@@ -257,7 +257,12 @@ int adapt_conv2d_grouped_layer_f32(const adapt_lut *lut, const float *x_dev, con
  *                  tables) returns ADAPT_ERR_UNSUPPORTED with next's copy untouched and needs the buffer.
  * `next` must have been prepared for N images of this layer's output size and have as many input channels as this
  * layer has output channels, and must be another handle than `w`; otherwise ADAPT_ERR_INVALID_ARGUMENT.  An ordinary call on a prepared handle with
- * another geometry ends its prepared state.  Results are identical to the unchained calls. */
+ * another geometry ends its prepared state.  Results are identical to the unchained calls.
+ * A handle remembers whether the call that last wrote its input copy applied ReLU (act = 1): all codes are then >= 0 and
+ * the consuming call streams only the table lines such codes can select.  That is decided when the consuming call is
+ * made; a recorded graph keeps the decision of the time of recording, so record producer and consumer together (or
+ * record the consumer after a producer with the same `act` has run).  These calls change state of `w` and `next`: do
+ * not run two chains over the same handles from two threads at once. */
 int adapt_conv2d_chain_prepare(const adapt_weights *w, int N, int H, int W, int stride_h, int stride_w, int pad_h,
                                int pad_w, int dil_h, int dil_w, void *stream);
 int adapt_conv2d_layer_chain_f32(const adapt_weights *w, const float *x_dev, float *y_dev, int N, int H, int W,
