@@ -507,6 +507,9 @@ def test_config1_linear(B):
     assert (host(acc) == want).all()
     y = B.adapt_dequant_i32(acc, c["scale"], 64, 128, 1)
     assert_f32_close(host(y), orc.dequant(want, c["scale"], 64, 128, 1))
+    # as bench.py times it: weights packed once, product on the packed handle
+    pw = B.adapt_weights_pack_linear(L, dev(c["W"]))
+    assert (host(B.adapt_approx_linear_packed(pw, dev(c["A"]))) == want).all()
 
 
 def test_config2_conv_full_size(B):
