@@ -948,6 +948,11 @@ LAYER_CONVT = [
     (2, 7, 5, 5, 5, 2, 2, 0),          # no border terms: rescaled inside the product kernel
     (2, 3, 5, 3, 2, 3, 2, 0),          # plain form
     (4, 10, 1, 1, 6, 4, 1, 0),         # single input pixel
+    # big-layer kernel, 4 rows per row slot; channel tiles that share an XCD between several row tiles:
+    (64, 32, 16, 16, 32, 4, 2, 1),     # 4 channel tiles, 16 row tiles per phase: the phases of a row tile stay on one XCD
+    (60, 32, 16, 16, 32, 4, 2, 1),     # 15 row tiles: the plain phase-fastest order
+    (256, 16, 16, 16, 8, 4, 2, 1),     # 1 channel tile, 64 row tiles
+    (252, 16, 16, 16, 5, 4, 2, 1),     # 63 row tiles, 5 of 8 channels
 ]
 
 
