@@ -22,7 +22,14 @@
 // lanes of a k-sub (16 row slots) read 16 different slots in every instruction - row slot r takes channel group
 // (q + r % 4) % 4 and, in read t, byte (t + r / 4) % 4 of it - so a read instruction is free of bank conflicts whatever
 // the activations are.  Two 64 KB buffers: while step s is read from one, the table of step s + 1 is copied
-// into the other by LDS-direct loads (no register round trip); every step ends with vmcnt(0) and a barrier.
+// into the other by LDS-direct loads (no register round trip); a step ends when the wave's part of that copy has landed
+// (a counted wait that leaves the newer activation loads in flight) and a barrier.
+//
+// What a step streams.  Steps run block by block (16 channels), the taps of a block one after the other.  Only the lines
+// that can be selected are copied (LinesParams::copy_lines: all, or the first half behind a ReLU).  Every table is new
+// to the L2 that serves it, so the workgroups that share a table touch it two steps ahead (one plain load per wave) and
+// start their copies at different chunks.  With the phases of a transposed convolution, the workgroups of one row
+// tile's phases run next to each other on one XCD, so that the L2 merges the interleaved pixels they write.
 //
 // Activations come from the x-major zero-padded copy (see pad_channels_last_kernel), which holds table line indices:
 // the R pixels x 4 channels of a lane and step are R / 4 loads of 16 bytes.
