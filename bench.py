@@ -418,7 +418,8 @@ def network_roofline(cfg_id, bits, macs, ms_per_step, ceilings, model_peak, gnet
         dom, bound = "lut_rows_kernel (recurrent step: product + cell, 100 launches)", "lds_gather16 (recurrence) + lds_read (input products)"
     else:
         t = 2.0 * macs / lds
-        dom = {3: "lut_lines_fast_kernel (128-byte lines; 19 launches of 18 - 30 us)", 5: "lut_quad_kernel<%d, 8, true>" % (4 if bits == 8 else 1),
+        dom = {3: "lut_lines_fast_kernel (32- and 64-channel layers) and lut_quad_kernel (16-channel layers); 19 launches of 15 - 23 us",
+               5: "lut_quad_kernel<%d, 8, true>" % (2 if bits == 8 else 1),
                6: "lut_grouped_tiled_kernel + lut_quad_kernel"}[cfg_id]
         bound = "lds_read"
     return dict(bound=bound, achieved=macs / (ms_per_step * 1e-3) / 1e12, peak=macs / t / 1e12, unit="Tlookup/s", frac=t / (ms_per_step * 1e-3),
