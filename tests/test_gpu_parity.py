@@ -1624,13 +1624,14 @@ def test_chained_conv_layers_match_unchained_and_oracle(B, case):
     assert e.value.code == -1
 
 
+@pytest.mark.parametrize("shape", [(32, 64, 32, 32), (16, 32, 16, 16)])      # big-layer kernel; 128-byte-line kernel
 @pytest.mark.parametrize("bits", [8, 7, 5])
-def test_chained_consumer_after_relu_and_after_no_activation(B, bits):
+def test_chained_consumer_after_relu_and_after_no_activation(B, bits, shape):
     """A consumer on the big-layer kernel copies only the first half of every table into LDS when the producing layer
     applied ReLU (all codes >= 0) and the whole table otherwise: the same two handles, the producer alternating between no
     activation (negative codes present) and ReLU, consumer output against the oracle every time."""
-    N, C, H, W = 32, 64, 32, 32
-    rng = np.random.default_rng(900 + bits)
+    N, C, H, W = shape
+    rng = np.random.default_rng(900 + bits + N)
     lut = wl.make_lut(bits)
     L = B.Lut(lut, bits)
     x = rng.standard_normal((N, C, H, W)).astype(np.float32)
