@@ -63,9 +63,13 @@ inline long long quad_cost(int R, int M, int tiles, int steps, int bits, int cu)
 // The quad kernel takes a product when its tables exist, the window moves one pixel at a time, the inner dimension has
 // at least QUAD_MIN_STEPS steps and some admissible R gives at least three quarters of the compute units a workgroup.
 // Measured inside networks (tables arrive cold): 9-step 3 x 3 layers of 16 channels and an 8-step 1 x 1 layer of 128
-// channels are 10 - 20 % faster on it than on the 128-byte-line kernels; layers that would cover only half the compute
-// units (or need the inner dimension split over workgroups) are not.
+// channels are 10 - 20 % faster on it than on the 128-byte-line kernels.  Layers that would cover half the compute units
+// or less run on it with the inner dimension split over workgroups (the ResNet-style 64-channel 8 x 8 layers as 4 slices
+// of 9 steps: 20 us with the kernel that adds the slices, against 27 us on the 128-byte-line kernels; the 32-channel
+// layers as 2 slices: a little faster too).  A layer that fills the chip unsplit is never split: 8 rows per row slot
+// x 2 slices measured the same as 4 rows unsplit at the benchmark layer, and slower inside the ResNet-style network.
 constexpr int QUAD_MIN_STEPS = 4;
+constexpr int QUAD_MIN_SLICE_STEPS = 8;
 
 inline LinesPlan plan_lines(const PlanIn &in) {
     const int M = in.M, cu = in.cu;
@@ -81,6 +85,23 @@ inline LinesPlan plan_lines(const PlanIn &in) {
             if (best.R == 0 || c < best_cost) { best.R = R; best_cost = c; }
         }
         if (best.R) return best;
+        // No R fills three quarters of the chip.  With half of it or less at 4 rows per row slot, slices of the inner
+        // dimension (at least QUAD_MIN_SLICE_STEPS steps each, at most 8 slices) go to workgroups of their own and a second
+        // kernel adds the partial sums - if that fills the chip.
+        if (quad_rows_ok(4, M, in.Wo)) {
+            const long long wgs = (long long)((M + 1023) / 1024) * in.tiles;
+            long long ks = cu / wgs;
+            if (ks > in.quad_steps / QUAD_MIN_SLICE_STEPS) ks = in.quad_steps / QUAD_MIN_SLICE_STEPS;
+            if (ks > 8) ks = 8;
+            if (ks >= 2) {
+                const int gps = (int)((in.quad_steps + ks - 1) / ks);
+                ks = (in.quad_steps + gps - 1) / gps;
+                if (ks >= 2 && wgs * ks * 4 >= 3LL * cu) {
+                    best.R = 4; best.ksplit = (int)ks; best.gps = gps;
+                    return best;
+                }
+            }
+        }
     }
     // 128-byte-line kernels: rows per lane R (a workgroup handles 128 R rows) as large as still gives every compute unit
     // a workgroup.  When even R = 8 leaves three quarters of them idle and the inner dimension is long enough, keep

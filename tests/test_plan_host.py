@@ -25,12 +25,12 @@ def test_resnet20_layers(plan):
     assert plan(1, 8, 0, 16, 16, 3, 3, 1, 128 * 32 * 32, 32, 1) == (QUAD, 1024, 1, 9, 256)
     # a 1x1 layer of 32 channels has 2 steps: below the quad kernel's minimum of 4
     assert plan(1, 8, 0, 16, 32, 1, 1, 1, 128 * 32 * 32, 32, 1)[0] != QUAD
-    # stage 2: 32 channels, 32768 rows: the quad kernel would cover half the compute units; 4 rows per lane on the
-    # 128-byte-line kernel
-    assert plan(1, 8, 0, 32, 32, 3, 3, 1, 128 * 16 * 16, 16, 1)[:3] == (FAST, 512, 1)
-    # stage 3: 64 channels, 8192 rows: inner dimension split over 4 workgroups
-    k, rows, ksplit, steps, wgs = plan(1, 8, 0, 64, 64, 3, 3, 1, 128 * 8 * 8, 8, 1)
-    assert (k, rows, ksplit, wgs) == (XMAJOR, 1024, 4, 256)
+    # stage 2: 32 channels, 32768 rows: unsplit the quad kernel would cover half the compute units: 2 slices of 9 steps
+    assert plan(1, 8, 0, 32, 32, 3, 3, 1, 128 * 16 * 16, 16, 1) == (QUAD, 1024, 2, 18, 256)
+    # stage 3: 64 channels, 8192 rows: a quarter of the compute units: 4 slices of 9 steps
+    assert plan(1, 8, 0, 64, 64, 3, 3, 1, 128 * 8 * 8, 8, 1) == (QUAD, 1024, 4, 36, 256)
+    # too few steps to slice (a 1x1 layer of 64 channels, 4 steps, on a quarter of the chip): 128-byte-line kernels
+    assert plan(1, 8, 0, 64, 64, 1, 1, 1, 128 * 8 * 8, 8, 1)[0] != QUAD
     # stride-2 layers never take the x-major copy
     assert plan(1, 8, 0, 32, 16, 3, 3, 1, 128 * 16 * 16, 16, 2)[0] in (FAST, GENERIC)
     assert plan(1, 8, 0, 64, 32, 3, 3, 1, 128 * 8 * 8, 8, 2)[0] in (FAST, GENERIC)
