@@ -252,9 +252,10 @@ int adapt_conv2d_grouped_layer_f32(const adapt_lut *lut, const float *x_dev, con
  *   next != NULL : y is ALSO written into the prepared workspace of `next` as its input copy, quantised with
  *                  s_next exactly as adapt_quantize_f32 would quantise y_dev.  y_dev is written too, unless it is NULL:
  *                  a caller that wants nothing but next's copy may pass y_dev == NULL with next != NULL.  That works
- *                  where the product kernel itself finishes the sums and writes the copy; a shape whose sums are
- *                  finished in a separate pass over the output (inner dimension split over workgroups, two-pass
- *                  tables) returns ADAPT_ERR_UNSUPPORTED with next's copy untouched and needs the buffer.
+ *                  where the product kernel, or the kernel that adds the sums of a layer whose inner dimension is
+ *                  split over workgroups, finishes the sums and writes the copy; a layer whose sums are finished in
+ *                  a separate pass over the output (two-pass tables; split layers whose output width or plane size is
+ *                  no multiple of 4) returns ADAPT_ERR_UNSUPPORTED with next's copy untouched and needs the buffer.
  * `next` must have been prepared for N images of this layer's output size and have as many input channels as this
  * layer has output channels, and must be another handle than `w`; otherwise ADAPT_ERR_INVALID_ARGUMENT.  An ordinary call on a prepared handle with
  * another geometry ends its prepared state.  Results are identical to the unchained calls.

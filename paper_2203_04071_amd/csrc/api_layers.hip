@@ -521,6 +521,15 @@ size_t quad_table_bytes(const LinesShape &q, int bits) {
     return (size_t)q.n_tiles * q.kh * q.kw * (q.Cp / adapt::QUAD_STEP) * ((size_t)adapt::QUAD_LINE_BYTES << bits);
 }
 
+// The kernel that adds split sums can run without an fp32 output buffer (only the next layer's copy is wanted) in its
+// four-elements-per-thread form: rescaled output with a chained copy, everything in whole quads and 16-byte aligned.
+static bool adding_kernel_without_output_ok(const LinesCall &c, const LayerIO *io) {
+    if (!io || !io->chain.buf || !io->deq) return false;
+    const int wo = io->chain_wo;
+    return c.out_elems < 0x7fffffffull && c.out_elems % 4 == 0 && c.out_inner % 4 == 0 && wo > 0 && wo % 4 == 0 && c.partial &&
+           ((reinterpret_cast<uintptr_t>(c.partial) | reinterpret_cast<uintptr_t>(io->resid)) & 15u) == 0;
+}
+
 int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], const int8_t *xt, const LinesCall &c,
               int32_t *out, hipStream_t s, const LayerIO *io = nullptr, bool may_fuse = true, bool *border_done = nullptr,
               bool *finished = nullptr) {
@@ -566,9 +575,9 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
     p.chain = chain_in_kernel ? io->chain : adapt::ChainOut{};
     // a caller that only wants the next layer's copy passes no output buffer; that works where the product kernel itself
     // finishes the sums and writes the copy (no partial sums, no separate finishing pass, residual aside)
-    if (!out && !chain_in_kernel)
+    if (!out && !chain_in_kernel && !(sums_elsewhere && fuse && storage == 0 && adding_kernel_without_output_ok(c, io)))
         return fail(ADAPT_ERR_UNSUPPORTED, "this layer shape finishes its sums in a separate pass over the output: y_dev is needed");
-    p.no_out = out ? 0 : 1;
+    p.no_out = (!out && !sums_elsewhere) ? 1 : 0;       // (partial sums are always stored)
     p.zsum = border_in_kernel ? c.zsum : nullptr;
     p.cv_s = fast_div((uint32_t)c.cv_s);
     p.cv_Ho = c.cv_Ho; p.cv_Wo = c.cv_Wo; p.cv_H = c.cv_H; p.cv_W = c.cv_W; p.cv_kh = c.cv_kh; p.cv_kw = c.cv_kw;
@@ -608,6 +617,8 @@ int run_lines(int bits, int storage, const LinesShape &q, uint4 *const dt[2], co
                                c.out_inner < 0x7fffffffull && c.out_channels < 0x7fffffffull && (!chained || wo % 4 == 0) &&
                                ((reinterpret_cast<uintptr_t>(c.partial) | reinterpret_cast<uintptr_t>(out) |
                                  reinterpret_cast<uintptr_t>(io->resid)) & 15u) == 0;
+            if (!out && !(quads && chained))
+                return fail(ADAPT_ERR_UNSUPPORTED, "this layer shape finishes its sums in a separate pass over the output: y_dev is needed");
             const size_t threads_needed = quads ? c.out_elems / 4 : c.out_elems;
             adapt::reduce_partials_kernel<<<ew_grid(threads_needed), adapt::EW_THREADS, 0, s>>>(
                 c.partial, pl.ksplit, c.out_elems, out, c.out_elems, half == 0 ? -1 : 16, (fuse && half == 0) ? 1 : 0, c.out_channels,

@@ -568,7 +568,7 @@ __global__ __launch_bounds__(EW_THREADS) void reduce_partials_kernel(const int32
                 if (act == 1) y[e] = y[e] > 0.0f ? y[e] : 0.0f;
                 else if (act == 2) y[e] = tanh_spec(y[e]);
             }
-            reinterpret_cast<float4 *>(out)[q] = make_float4(y[0], y[1], y[2], y[3]);
+            if (out) reinterpret_cast<float4 *>(out)[q] = make_float4(y[0], y[1], y[2], y[3]);      // (nullptr: only the copy is wanted)
             if (chain.buf) {
                 const uint32_t oy = d_wo.div(pix), ox = pix - oy * (uint32_t)chain_wo;
 #pragma unroll

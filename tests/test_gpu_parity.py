@@ -1659,32 +1659,34 @@ def test_chained_consumer_after_relu_and_after_no_activation(B, bits, shape):
 
 
 def test_refused_producer_call_does_not_change_what_the_consumer_assumes(B):
-    """A producer call that is refused (no output buffer on a shape that needs one) writes nothing into the next layer's
-    copy, so it must not change what the consumer takes the copy to hold: the copy still has the codes of an earlier
-    producer WITHOUT ReLU (negative codes present), and the consumer has to read whole tables."""
-    bits, N, C, H, W = 8, 16, 64, 8, 8          # 1024 rows: the producer splits its inner dimension and needs its output buffer
+    """A producer call that is refused (no output buffer on a layer that needs one: its table takes two passes, so its
+    sums are finished in a separate pass over the output) writes nothing into the next layer's copy, so it must not
+    change what the consumer takes the copy to hold: the copy still has the codes of an earlier producer call WITHOUT
+    ReLU (negative codes present), and the consumer has to read whole tables."""
+    bits, N, C, H, W = 8, 16, 64, 16, 16
     rng = np.random.default_rng(77)
     lut = wl.make_lut(bits)
-    L = B.Lut(lut, bits)
+    lut_wide = rng.integers(-2**20, 2**20, size=(256, 256)).astype(np.int32)       # entries beyond 16 bits: two passes
+    L, LW = B.Lut(lut, bits), B.Lut(lut_wide, bits)
     x = rng.standard_normal((N, C, H, W)).astype(np.float32)
     w0 = wl.random_i8(rng, (C, C, 3, 3), bits, "gauss")
     w1 = wl.random_i8(rng, (C, C, 3, 3), bits, "gauss")
     th = orc.host_threads()
     s0 = orc.scale_from_amax(orc.absmax(x), bits)
-    y0 = orc.dequant(orc.approx_conv2d(lut, bits, orc.quantize(x, s0, bits), w0, (1, 1), (1, 1), threads=th), np.float32(s0) * np.float32(0.01),
-                     N, C, H * W)
+    so0 = np.float32(s0) * np.float32(1e-6)
+    y0 = orc.dequant(orc.approx_conv2d(lut_wide, bits, orc.quantize(x, s0, bits), w0, (1, 1), (1, 1), threads=th), so0, N, C, H * W)
     s1 = orc.scale_from_amax(orc.absmax(y0), bits)
     q1 = orc.quantize(y0, s1, bits)
     assert (q1 < 0).any()
     want = orc.dequant(orc.approx_conv2d(lut, bits, q1, w1, (1, 1), (1, 1), threads=th), np.float32(s1) * np.float32(0.01), N, C, H * W)
-    p0, p1 = B.adapt_weights_pack_conv2d(L, dev(w0)), B.adapt_weights_pack_conv2d(L, dev(w1))
+    p0, p1 = B.adapt_weights_pack_conv2d(LW, dev(w0)), B.adapt_weights_pack_conv2d(L, dev(w1))
     B.adapt_conv2d_chain_prepare(p1, N, H, W, (1, 1), (1, 1))
     o0 = torch.empty((N, C, H, W), dtype=torch.float32, device="cuda")
     o1 = torch.empty((N, C, H, W), dtype=torch.float32, device="cuda")
-    B.adapt_conv2d_layer_chain_f32(p0, dev(x), s0, np.float32(s0) * np.float32(0.01), o0, (1, 1), (1, 1), act=B.ACT_NONE, next_pw=p1, s_next=s1)
+    B.adapt_conv2d_layer_chain_f32(p0, dev(x), s0, so0, o0, (1, 1), (1, 1), act=B.ACT_NONE, next_pw=p1, s_next=s1)
+    assert bits_equal(host(o0), y0)
     with pytest.raises(B.AdaptError) as e:
-        B.adapt_conv2d_layer_chain_f32(p0, dev(x), s0, np.float32(s0) * np.float32(0.01), None, (1, 1), (1, 1), act=B.ACT_RELU, next_pw=p1,
-                                       s_next=s1)
+        B.adapt_conv2d_layer_chain_f32(p0, dev(x), s0, so0, None, (1, 1), (1, 1), act=B.ACT_RELU, next_pw=p1, s_next=s1)
     assert e.value.code == -2
     B.adapt_conv2d_layer_chain_f32(p1, None, s1, np.float32(s1) * np.float32(0.01), o1, (1, 1), (1, 1), in_shape=(N, H, W))
     assert bits_equal(host(o1), want)
