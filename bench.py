@@ -418,7 +418,7 @@ def network_roofline(cfg_id, bits, macs, ms_per_step, ceilings, model_peak, gnet
         dom, bound = "lut_rows_kernel (recurrent step: product + cell, 100 launches)", "lds_gather16 (recurrence) + lds_read (input products)"
     else:
         t = 2.0 * macs / lds
-        dom = {3: "lut_lines_fast_kernel (32- and 64-channel layers) and lut_quad_kernel (16-channel layers); 19 launches of 15 - 23 us",
+        dom = {3: "lut_quad_kernel (stride-1 layers; the 32- and 64-channel ones in slices + reduce_partials_kernel); 19 layers of 13 - 23 us",
                5: "lut_quad_kernel<%d, 8, true>" % (2 if bits == 8 else 1),
                6: "lut_grouped_tiled_kernel + lut_quad_kernel"}[cfg_id]
         bound = "lds_read"
