@@ -252,7 +252,11 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
     const uint32_t pf_voff =
         128u * (uint32_t)min(((rest / pf_span) & (pf_share - 1)) * pf_per_wg + wave * pf_per_wave + min(lane, pf_per_wave - 1), pf_lines - 1);
     uint32_t pf_sink = 0;
+    // (tables of one copy operation - 16 KB or less - are not prefetched: the extra load per wave and step costs more
+    // there than the copies' wait for memory, 3 % of a step)
+    constexpr int NP = DOPS >= 2 ? 1 : 0;
     auto prefetch = [&](int step_) {
+        if constexpr (NP == 0) return;
         const int step = step_ < nsteps ? step_ : nsteps - 1;
         asm volatile("global_load_dword %[d], %[vo], %[sa]" : [d] "+v"(pf_sink) : [vo] "v"(pf_voff), [sa] "s"(dt + (size_t)(unsigned)step * table_bytes));
     };
@@ -301,11 +305,11 @@ __global__ __launch_bounds__(LINES_THREADS) void lut_quad_kernel(const LinesPara
     // End of a step: this wave's part of the next table has landed (its copy operations were issued BEFORE the step's
     // activation loads, and a wave's memory operations retire in order, so all but the newest NL are done); the
     // activation loads stay in flight across the barrier and are waited for where the next step first needs them.
-    // Per step a wave issues, in this order: DOPS copy operations, NL activation loads, one prefetch load.
-    auto step_end = [&]() { asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" : : "n"(NL + 1) : "memory"); };
+    // Per step a wave issues, in this order: DOPS copy operations, NL activation loads, NP prefetch loads.
+    auto step_end = [&]() { asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" : : "n"(NL + NP) : "memory"); };
     // Start of a step, after its copy operations and loads have been issued: the activations requested one step ago
-    // (the oldest NL of the 2 (NL + 1) + DOPS operations in flight) have arrived.
-    auto acts_ready = [&]() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(DOPS + NL + 2) : "memory"); };
+    // (the oldest NL of the 2 (NL + NP) + DOPS operations in flight) have arrived.
+    auto acts_ready = [&]() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(DOPS + NL + 2 * NP) : "memory"); };
 
     // position of a step's activations: step = block * taps + tap (Cc blocks of 16 channels = 4 channel groups of the copy)
     int bi = s_begin / p.taps;
