@@ -130,16 +130,19 @@ def _f(x):
     return np.float32(x)
 
 
-def _graph_step(gnet, net, x, eager):
-    """The network configurations are chains of many small launches: one step = one replay of the forward pass recorded
-    into a HIP graph (same kernels, same order); --eager launches them one by one instead."""
-    if eager:
+def _graph_step(gnet, net, x, mode, many_small_launches):
+    """A step of a network configuration is either one replay of the forward pass recorded into a HIP graph or the same
+    kernels launched one by one.  Default: the graph where the pass is a chain of many small launches (ResNet-style CNN:
+    34, recurrent layers: 200), launches one by one where it is a handful of kernels (measured: config 1 16 against 20 us,
+    the separable block 52 against 57 us, the generator the same on most boxes and 6 % faster on one; a replay costs a
+    few microseconds by itself).  --eager / --graph force one or the other."""
+    if mode == "eager" or (mode is None and not many_small_launches):
         return lambda: net.forward(x)
     cap = gnet.Captured(net, x)
     return lambda: cap.replay()
 
 
-def build_step(cfg_id, bits, torch, B, gnet, wl, eager=False):
+def build_step(cfg_id, bits, torch, B, gnet, wl, eager=False, mode=None):
     """Returns (step_fn, core_fn, macs, workload_name, dtype) for a configuration.
     step_fn(): one pass of the whole path; core_fn(): only the dominant table-lookup call."""
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
@@ -159,7 +162,7 @@ def build_step(cfg_id, bits, torch, B, gnet, wl, eager=False):
             def forward(self, a):
                 B.adapt_approx_linear_packed(pw, a, out=acc)
                 return B.adapt_dequant_i32(acc, c["scale"], 64, 128, 1, out=y)
-        step = _graph_step(gnet, _Step(), A, eager)
+        step = _graph_step(gnet, _Step(), A, mode, False)
         return step, core, 64 * 256 * 128, "config1: approx_linear 64x256x128, 8-bit table", (L, pw)
     if cfg_id == 2:
         c = wl.config2()
@@ -210,28 +213,28 @@ def build_step(cfg_id, bits, torch, B, gnet, wl, eager=False):
         net = gnet.ResNet20(c)
         x = dev(c["x"])
         net.forward(x)            # calibration pass (host reads), scales frozen afterwards
-        step = _graph_step(gnet, net, x, eager)
+        step = _graph_step(gnet, net, x, mode, True)
         return step, None, gnet.lut_macs_resnet20(128), "config3: ResNet-20-style CNN, batch 128, 8-bit table", net
     if cfg_id == 4:
         c = wl.config4()
         net = gnet.LSTM(c)
         x = dev(c["x"])
         net.forward(x)
-        step = _graph_step(gnet, net, x, eager)
+        step = _graph_step(gnet, net, x, mode, True)
         return step, None, gnet.lut_macs_lstm(100, 64, 512, 512), "config4: LSTM 512/512, seq 100, batch 64, 7-bit table", net
     if cfg_id == 5:
         c = wl.config5(bits=bits)
         net = gnet.DCGAN(c)
         z = dev(c["z"])
         net.forward(z)
-        step = _graph_step(gnet, net, z, eager)
+        step = _graph_step(gnet, net, z, mode, False)
         return step, None, gnet.lut_macs_dcgan(256, c["plan"]), f"config5: DCGAN-style generator, batch 256, {bits}-bit table", net
     if cfg_id == 6:     # beyond the five baseline configurations: separable convolution block (Sec. III-B, eq. (1))
         c = wl.separable_workload(batch=32, cin=128, cout=128, hw=32)
         net = gnet.SeparableConv(c)
         x = dev(c["x"])
         net.forward(x)
-        step = _graph_step(gnet, net, x, eager)
+        step = _graph_step(gnet, net, x, mode, False)
         macs = wl.lut_macs_conv2d(32, 128, 32, 32, 128, 3, 3, 1, 1, 1, 1, groups=128) + wl.lut_macs_conv2d(32, 128, 32, 32, 128, 1, 1, 1, 1, 0, 0)
         return step, None, macs, "extra: separable convolution 3x3 depthwise + 1x1, batch 32, 128->128 ch, 32x32, 8-bit table", net
     if cfg_id == 7:     # GRU layer at the size of the LSTM configuration (Sec. III-B "RNN Layer")
@@ -239,7 +242,7 @@ def build_step(cfg_id, bits, torch, B, gnet, wl, eager=False):
         net = gnet.Recurrent(c, "gru")
         x = dev(c["x"])
         net.forward(x)
-        step = _graph_step(gnet, net, x, eager)
+        step = _graph_step(gnet, net, x, mode, True)
         return step, None, 100 * 64 * 3 * 512 * (512 + 512), "extra: GRU 512/512, seq 100, batch 64, 7-bit table", net
     if cfg_id in (8, 9):    # the layer of configuration 2 with 12-bit operands: table in device memory (8) / Mitchell function (9)
         c = wl.config2()
@@ -443,7 +446,9 @@ def main():
     ap.add_argument("--other-steps", type=int, default=20, help="timed steps for each of the other configurations of the default run")
     ap.add_argument("--prewarm-ms", type=float, default=300.0,
                     help="untimed steps for this long before the warm-up steps, so that the device clocks have settled (0: none)")
-    ap.add_argument("--eager", action="store_true", help="network configurations: launch kernel by kernel instead of replaying a HIP graph")
+    ap.add_argument("--eager", action="store_true", help="network configurations: launch kernel by kernel (default for configs 1, 5, 6); "
+                    "config 2: the separate calls instead of the fused layer call")
+    ap.add_argument("--graph", action="store_true", help="network configurations: replay a HIP graph (default for configs 3, 4, 7)")
     ap.add_argument("--probe-report", action="store_true", help="run every ceiling probe and print their rates as one JSON line; nothing else")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run three plain 64 MiB device-to-device copies (what FETCH_SIZE / WRITE_SIZE are scaled by)")
@@ -473,7 +478,7 @@ def main():
         return
     # ceilings of this device, measured now (headline and network configurations price their kernels against them)
     ceilings = run_probes() if args.config <= 7 and not args.no_probes else None
-    step, core, macs, name, _keep = build_step(args.config, args.bits, torch, B, gnet, wl, args.eager)
+    step, core, macs, name, _keep = build_step(args.config, args.bits, torch, B, gnet, wl, args.eager, "eager" if args.eager else ("graph" if args.graph else None))
 
     def timed(step_fn, steps, warmup, prewarm_ms):
         # bring the device to its running clocks before anything is measured (a cold GPU runs the first tens of
