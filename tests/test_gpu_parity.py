@@ -1477,6 +1477,76 @@ def test_random_shapes_match_oracle(B, seed):
     assert not bad, bad
 
 
+@pytest.mark.parametrize("seed", [41, 42])
+def test_random_long_products_match_oracle(B, seed):
+    """Seeded random shapes with thousands of rows and 16 to 128 channels - what the kernels that stream derived tables
+    take, unsplit or with the inner dimension in slices: convolutions (filters 1 to 5 wide, vertical stride, dilation,
+    padding; as integer products and as fp32 layers), long linear products, stride-2 transposed layers with every
+    activation."""
+    rng = np.random.default_rng(seed)
+    luts = {b: wl.make_lut(b) for b in (5, 6, 7, 8)}
+    L = {b: B.Lut(luts[b], b) for b in luts}
+    th = orc.host_threads()
+    bad = []
+    for it in range(60):
+        bits = int(rng.choice([5, 6, 7, 8])); lut = luts[bits]; LL = L[bits]
+        kind = str(rng.choice(["conv", "conv_layer", "linear", "convt_layer"]))
+        if kind in ("conv", "conv_layer"):
+            N = int(rng.choice([4, 8, 16, 32, 64, 100])); Cin = int(rng.choice([16, 32, 48, 64, 128, 20, 40]))
+            Cout = int(rng.choice([5, 8, 16, 24, 32, 64, 70]))
+            H = int(rng.choice([8, 10, 12, 16, 20, 32])); W = int(rng.choice([8, 12, 16, 20, 32, 36]))
+            kh = int(rng.choice([1, 3, 3, 5])); kw = int(rng.choice([1, 3, 3, 5])); dh = int(rng.choice([1, 1, 2])); dw = int(rng.choice([1, 1, 2]))
+            sh = int(rng.choice([1, 1, 2])); ph = int(rng.integers(0, 3))
+            pw_ = (dw * (kw - 1)) // 2 if rng.random() < 0.7 else int(rng.integers(0, 3))
+            if H + 2 * ph < dh * (kh - 1) + 1 or W + 2 * pw_ < dw * (kw - 1) + 1:
+                continue
+            w = wl.random_i8(rng, (Cout, Cin, kh, kw), bits, "gauss")
+            desc = (kind, bits, N, Cin, H, W, Cout, kh, kw, sh, ph, pw_, dh, dw)
+            pk = B.adapt_weights_pack_conv2d(LL, dev(w))
+            if kind == "conv":
+                x = wl.random_i8(rng, (N, Cin, H, W), bits, "gauss")
+                want = orc.approx_conv2d(lut, bits, x, w, (sh, 1), (ph, pw_), (dh, dw), 1, threads=th)
+                ok = (host(B.adapt_approx_conv2d_packed(pk, dev(x), (sh, 1), (ph, pw_), (dh, dw))) == want).all()
+            else:
+                xf = rng.standard_normal((N, Cin, H, W)).astype(np.float32)
+                s_x = orc.scale_from_amax(orc.absmax(xf), bits)
+                want = orc.approx_conv2d(lut, bits, orc.quantize(xf, s_x, bits), w, (sh, 1), (ph, pw_), (dh, dw), 1, threads=th)
+                n_, c_, h_, w_ = want.shape
+                bias = rng.standard_normal(Cout).astype(np.float32); s_o = np.float32(s_x) * np.float32(0.02)
+                act = int(rng.choice([0, 1]))
+                y = orc.dequant(want, s_o, n_, c_, h_ * w_, bias)
+                if act:
+                    y = orc.relu(y)
+                got = host(B.adapt_conv2d_layer_f32(pk, dev(xf), s_x, s_o, (sh, 1), (ph, pw_), (dh, dw), bias=dev(bias), act=act))
+                ok = bits_equal(got, y.reshape(got.shape))
+        elif kind == "linear":
+            M = int(rng.choice([4096, 6400, 8192, 10000, 16384])); K = int(rng.choice([64, 96, 128, 200, 512])); N = int(rng.choice([8, 16, 30, 64]))
+            a = wl.random_i8(rng, (M, K), bits, "gauss"); w = wl.random_i8(rng, (N, K), bits, "gauss")
+            desc = (kind, bits, M, K, N)
+            pw = B.adapt_weights_pack_linear(LL, dev(w))
+            ok = (host(B.adapt_approx_linear_packed(pw, dev(a))) == orc.approx_linear(lut, bits, a, w, threads=th)).all()
+        else:
+            N = int(rng.choice([8, 32, 64, 128])); Cin = int(rng.choice([16, 24, 32, 64, 128])); Cout = int(rng.choice([3, 8, 16, 32, 64]))
+            H = int(rng.choice([4, 8, 16])); W = int(rng.choice([4, 8, 16])); k = int(rng.choice([2, 4, 4, 6])); p = int(rng.choice([0, 1, 2]))
+            if (H - 1) * 2 - 2 * p + k < 1 or (W - 1) * 2 - 2 * p + k < 1:
+                continue
+            w = wl.random_i8(rng, (Cin, Cout, k, k), bits, "gauss")
+            xf = rng.standard_normal((N, Cin, H, W)).astype(np.float32)
+            desc = (kind, bits, N, Cin, H, W, Cout, k, p)
+            s_x = orc.scale_from_amax(orc.absmax(xf), bits)
+            want = orc.approx_conv_transpose2d(lut, bits, orc.quantize(xf, s_x, bits), w, 2, p, threads=th)
+            n_, c_, h_, w_ = want.shape
+            s_o = np.float32(s_x) * np.float32(0.02); act = int(rng.choice([0, 1, 2]))
+            y = orc.dequant(want, s_o, n_, c_, h_ * w_)
+            y = orc.relu(y) if act == 1 else (orc.tanh(y) if act == 2 else y)
+            pk = B.adapt_weights_pack_conv_transpose2d(LL, dev(w), 2)
+            got = host(B.adapt_conv_transpose2d_layer_f32(pk, dev(xf), s_x, s_o, p, act=act))
+            ok = bits_equal(got, y.reshape(got.shape))
+        if not ok:
+            bad.append(desc)
+    assert not bad, bad
+
+
 @pytest.mark.parametrize("seed", [21, 22])
 def test_random_grouped_layers_match_oracle(B, seed):
     """Seeded random depthwise-style layers through the one-kernel layer call (fp32 in, scalar or per-channel output
