@@ -126,6 +126,64 @@ def probe_report():
     print(json.dumps(dict(cus=cus, clock_ghz_assumed=2.4, probes=out)))
 
 
+def elementwise_report(torch, B, elements):
+    """--elementwise-report: the HBM-bound kernels of the path (range, quantiser, rescaling, histogram, fp32 glue) on a
+    tensor far larger than the caches, each timed with events on the launch stream over back-to-back launches, beside a
+    plain device-to-device copy of the same tensor timed the same way.  One JSON line: bytes per launch (what the
+    operation has to read and write), GB/s, and that rate as a fraction of the copy's and of the published 8 TB/s."""
+    n = int(elements)
+    g = torch.Generator(device="cuda").manual_seed(7)
+    x = torch.randn(n, device="cuda", generator=g)
+    x2 = torch.randn(n, device="cuda", generator=g)
+    y = torch.empty_like(x)
+    q = torch.empty(n, dtype=torch.int8, device="cuda")
+    acc = torch.randint(-1 << 20, 1 << 20, (n,), dtype=torch.int32, device="cuda", generator=g)
+    amax = torch.zeros(1, device="cuda")
+    B.adapt_absmax_f32(x, amax_out=amax)
+    torch.cuda.synchronize()
+    a = float(amax.item())
+    scale = a / 127.0
+    counts = torch.zeros(2048, dtype=torch.int32, device="cuda")     # (accumulated into: 33 launches stay far below 2^32 per bin)
+    chans = 64
+    inner = n // (16 * chans)
+    if 16 * chans * inner != n:
+        raise SystemExit("bench.py: --elements must be a multiple of 1024")
+    bias = torch.randn(chans, device="cuda", generator=g)
+    ops = [
+        ("copy (torch copy_, fp32 -> fp32)", 8 * n, lambda: y.copy_(x)),
+        ("absmax", 4 * n, lambda: B.adapt_absmax_f32(x, amax_out=amax)),
+        ("quantize fp32 -> int8", 5 * n, lambda: B.adapt_quantize_f32(x, scale, 8, out=q)),
+        ("dequant int32 -> fp32 (+ bias)", 8 * n, lambda: B.adapt_dequant_i32(acc, 1e-3, 16, chans, inner, bias=bias, out=y)),
+        ("relu", 8 * n, lambda: B.adapt_relu_f32(x, out=y)),
+        ("add (residual)", 12 * n, lambda: B.adapt_add_f32(x, x2, out=y)),
+        ("histogram of |x|, 2048 bins", 4 * n, lambda: B.adapt_histogram_abs_f32(x, a, 2048, counts=counts)),
+    ]
+    rows = []
+    copy_rate = None
+    for name, nbytes, fn in ops:
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        reps = 10
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        best = None
+        for _ in range(3):
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            best = ms if best is None or ms < best else best
+        rate = nbytes / (best * 1e-3)
+        if copy_rate is None:
+            copy_rate = rate
+        rows.append(dict(op=name, bytes_per_launch=nbytes, ms=round(best, 4), GB_s=round(rate / 1e9, 1),
+                         frac_of_copy=round(rate / copy_rate, 3), frac_of_8TBs=round(rate / 8e12, 3)))
+    print(json.dumps(dict(elements=n, note="events on torch's current stream, which is the stream these calls launch on; best of 3 blocks of 10 launches",
+                          ops=rows)))
+
+
 def _f(x):
     return np.float32(x)
 
@@ -450,6 +508,9 @@ def main():
                     "config 2: the separate calls instead of the fused layer call")
     ap.add_argument("--graph", action="store_true", help="network configurations: replay a HIP graph (default for configs 3, 4, 7)")
     ap.add_argument("--probe-report", action="store_true", help="run every ceiling probe and print their rates as one JSON line; nothing else")
+    ap.add_argument("--elementwise-report", action="store_true",
+                    help="time the HBM-bound element-wise kernels on a large tensor beside a plain copy and print one JSON line; nothing else")
+    ap.add_argument("--elements", type=float, default=float(1 << 26), help="tensor size for --elementwise-report (default 64 Mi elements)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run three plain 64 MiB device-to-device copies (what FETCH_SIZE / WRITE_SIZE are scaled by)")
     ap.add_argument("--traffic-bytes", type=float, default=None,
@@ -467,6 +528,9 @@ def main():
     torch.cuda.set_device(0)
     if args.probe_report:
         probe_report()
+        return
+    if args.elementwise_report:
+        elementwise_report(torch, B, args.elements)
         return
     if args.copy_calibration:
         a = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")

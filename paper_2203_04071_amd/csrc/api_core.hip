@@ -174,7 +174,8 @@ int adapt_histogram_abs_f32(const float *x_dev, size_t n, float amax, int bins, 
     if (!counts_dev || (!x_dev && n)) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_histogram_abs_f32: NULL pointer");
     if (n == 0) return ADAPT_OK;
     const float width = amax / (float)bins;
-    adapt::histogram_abs_kernel<<<ew_grid(n / 8 + 1), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, n, width, bins, counts_dev);
+    const int vec = (reinterpret_cast<uintptr_t>(x_dev) & 15u) == 0 ? 1 : 0;
+    adapt::histogram_abs_kernel<<<ew_grid(n / 8 + 1), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, n, width, bins, counts_dev, vec);
     HIP_TRY(hipGetLastError());
     return ADAPT_OK;
 }
@@ -235,7 +236,8 @@ int adapt_entropy_from_histogram(const uint32_t *counts_dev, int bins, float ama
 int adapt_relu_f32(const float *x_dev, float *y_dev, size_t n, void *stream) {
     if ((!x_dev || !y_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_relu_f32: NULL pointer");
     if (!n) return ADAPT_OK;
-    adapt::relu_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, y_dev, n);
+    const int vec = ((reinterpret_cast<uintptr_t>(x_dev) | reinterpret_cast<uintptr_t>(y_dev)) & 15u) == 0 ? 1 : 0;
+    adapt::relu_kernel<<<ew_grid(n / 4 + 1), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(x_dev, y_dev, n, vec);
     HIP_TRY(hipGetLastError());
     return ADAPT_OK;
 }
@@ -243,7 +245,8 @@ int adapt_relu_f32(const float *x_dev, float *y_dev, size_t n, void *stream) {
 int adapt_add_f32(const float *a_dev, const float *b_dev, float *y_dev, size_t n, int relu, void *stream) {
     if ((!a_dev || !b_dev || !y_dev) && n) return fail(ADAPT_ERR_INVALID_ARGUMENT, "adapt_add_f32: NULL pointer");
     if (!n) return ADAPT_OK;
-    adapt::add_kernel<<<ew_grid(n), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(a_dev, b_dev, y_dev, n, relu);
+    const int vec = ((reinterpret_cast<uintptr_t>(a_dev) | reinterpret_cast<uintptr_t>(b_dev) | reinterpret_cast<uintptr_t>(y_dev)) & 15u) == 0 ? 1 : 0;
+    adapt::add_kernel<<<ew_grid(n / 4 + 1), adapt::EW_THREADS, 0, (hipStream_t)stream>>>(a_dev, b_dev, y_dev, n, relu, vec);
     HIP_TRY(hipGetLastError());
     return ADAPT_OK;
 }

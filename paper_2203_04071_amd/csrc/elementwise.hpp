@@ -30,26 +30,40 @@ static __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, size_t n) {     
 // combine is an integer atomic max; NaNs fail the comparison and are skipped.
 static __global__ __launch_bounds__(EW_THREADS) void absmax_kernel(const float *__restrict__ x, size_t n,
                                                             uint32_t *__restrict__ out_bits, int vec) {
+    __shared__ float wave_max[EW_THREADS / 64];
     float m = 0.0f;
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
     const size_t n4 = vec ? n / 4 : 0;   // vec: x is 16-byte aligned
     const float4 *x4 = reinterpret_cast<const float4 *>(x);
-    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n4; i += stride) {
-        const float4 v = x4[i];
+    auto fold = [&](const float4 v) {
         float a = fabsf(v.x); if (a > m) m = a;
         a = fabsf(v.y); if (a > m) m = a;
         a = fabsf(v.z); if (a > m) m = a;
         a = fabsf(v.w); if (a > m) m = a;
+    };
+    size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    for (; i + 3 * stride < n4; i += 4 * stride) {      // four loads in flight per lane
+        const float4 v0 = x4[i], v1 = x4[i + stride], v2 = x4[i + 2 * stride], v3 = x4[i + 3 * stride];
+        fold(v0); fold(v1); fold(v2); fold(v3);
     }
-    for (size_t i = n4 * 4 + (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
-        const float a = fabsf(x[i]);
+    for (; i < n4; i += stride) fold(x4[i]);
+    for (size_t j = n4 * 4 + (size_t)blockIdx.x * EW_THREADS + threadIdx.x; j < n; j += stride) {
+        const float a = fabsf(x[j]);
         if (a > m) m = a;
     }
     for (int off = 32; off > 0; off >>= 1) {
         const float o = __shfl_xor(m, off, 64);
         if (o > m) m = o;
     }
-    if ((threadIdx.x & 63) == 0) atomicMax(out_bits, __float_as_uint(m));
+    // one atomic per workgroup: thousands of them on one address are what a short launch would otherwise wait for
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < EW_THREADS / 64; ++w)
+            if (wave_max[w] > m) m = wave_max[w];
+        atomicMax(out_bits, __float_as_uint(m));
+    }
 }
 
 __device__ __forceinline__ int quant1(float x, float scale, float Q) {
@@ -135,18 +149,24 @@ static __global__ __launch_bounds__(EW_THREADS) void dequant_pc_kernel(const int
 // (both IEEE fp32 divisions); NaN is not counted.  Per-workgroup histogram in LDS (bins <= 4096), then one atomic per
 // non-empty bin.
 static __global__ __launch_bounds__(EW_THREADS) void histogram_abs_kernel(const float *__restrict__ x, size_t n, float width, int bins,
-                                                                   uint32_t *__restrict__ counts) {
+                                                                   uint32_t *__restrict__ counts, int vec) {
     __shared__ uint32_t h[4096];
     for (int b = threadIdx.x; b < bins; b += EW_THREADS) h[b] = 0;
     __syncthreads();
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
-    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
-        const float a = fabsf(x[i]);
-        if (a != a) continue;
+    auto count = [&](float v) {
+        const float a = fabsf(v);
+        if (a != a) return;
         const float t = a / width;
         const int b = t >= (float)bins ? bins - 1 : (int)t;
         atomicAdd(&h[b < bins ? b : bins - 1], 1u);
+    };
+    const size_t n4 = vec ? n / 4 : 0;      // vec: x is 16-byte aligned
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n4; i += stride) {
+        const float4 v = reinterpret_cast<const float4 *>(x)[i];
+        count(v.x); count(v.y); count(v.z); count(v.w);
     }
+    for (size_t i = n4 * 4 + (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) count(x[i]);
     __syncthreads();
     for (int b = threadIdx.x; b < bins; b += EW_THREADS)
         if (h[b]) atomicAdd(&counts[b], h[b]);
@@ -284,17 +304,32 @@ static __global__ __launch_bounds__(EW_THREADS) void dequant_kernel(const int32_
     }
 }
 
-static __global__ __launch_bounds__(EW_THREADS) void relu_kernel(const float *x, float *y, size_t n) {
+// vec: every pointer is 16-byte aligned - four elements per lane and iteration (the same operation on each element;
+// y may be x itself)
+static __global__ __launch_bounds__(EW_THREADS) void relu_kernel(const float *x, float *y, size_t n, int vec) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
-    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
+    const size_t n4 = vec ? n / 4 : 0;
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n4; i += stride) {
+        float4 v = reinterpret_cast<const float4 *>(x)[i];
+        v.x = v.x > 0.0f ? v.x : 0.0f; v.y = v.y > 0.0f ? v.y : 0.0f; v.z = v.z > 0.0f ? v.z : 0.0f; v.w = v.w > 0.0f ? v.w : 0.0f;
+        reinterpret_cast<float4 *>(y)[i] = v;
+    }
+    for (size_t i = n4 * 4 + (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
         const float v = x[i];
         y[i] = v > 0.0f ? v : 0.0f;
     }
 }
 
-static __global__ __launch_bounds__(EW_THREADS) void add_kernel(const float *a, const float *b, float *y, size_t n, int relu) {
+static __global__ __launch_bounds__(EW_THREADS) void add_kernel(const float *a, const float *b, float *y, size_t n, int relu, int vec) {
     const size_t stride = (size_t)gridDim.x * EW_THREADS;
-    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
+    const size_t n4 = vec ? n / 4 : 0;
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n4; i += stride) {
+        const float4 p = reinterpret_cast<const float4 *>(a)[i], q = reinterpret_cast<const float4 *>(b)[i];
+        float4 v = make_float4(p.x + q.x, p.y + q.y, p.z + q.z, p.w + q.w);
+        if (relu) { v.x = v.x > 0.0f ? v.x : 0.0f; v.y = v.y > 0.0f ? v.y : 0.0f; v.z = v.z > 0.0f ? v.z : 0.0f; v.w = v.w > 0.0f ? v.w : 0.0f; }
+        reinterpret_cast<float4 *>(y)[i] = v;
+    }
+    for (size_t i = n4 * 4 + (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) {
         float v = a[i] + b[i];
         if (relu) v = v > 0.0f ? v : 0.0f;
         y[i] = v;
