@@ -571,7 +571,7 @@ def main():
     traffic = args.traffic_bytes
 
     def lookup_context(rate):
-        """The figure BASELINE names: lookups per second against one 2-byte lookup per bank-lane and clock."""
+        """The metric's own model: lookups per second against one 2-byte lookup per bank-lane and clock."""
         d = dict(achieved_Tlookup_s=rate / 1e12, model_peak_Tlookup_s=model_peak / 1e12, frac_of_model=rate / model_peak,
                  model=f"{cus} CUs x {LDS_LANES_PER_CLK_PER_CU} LDS bank-lanes/clk x {MODEL_CLOCK_GHZ} GHz; 1 lookup (2 B) per LUT-MAC")
         if ceilings:
