@@ -512,6 +512,39 @@ def test_config1_linear(B):
     assert (host(B.adapt_approx_linear_packed(pw, dev(c["A"]))) == want).all()
 
 
+@pytest.mark.parametrize("shape", [(64, 256, 128), (1, 64, 10), (130, 512, 24), (3000, 96, 40), (100, 100, 7), (64, 260, 16), (65, 1024, 130)])
+@pytest.mark.parametrize("table", ["8-bit", "6-bit two-pass"])
+def test_small_linear_layer_from_fp32(B, shape, table):
+    """Linear layers below the streamed-table threshold as one call from fp32 activations (quantiser, whole-table product
+    with the rescaling in its epilogue, or - two-pass table - a finishing pass): inner dimensions whose slices per lane
+    are whole words and ones that are not (7 and 17 elements), a matrix on a 16-byte boundary and the same 4 bytes off
+    it, ties of the quantiser.  The oracle's quantiser, product, rescaling, bias and ReLU, bit for bit."""
+    M, K, N = shape
+    rng = np.random.default_rng(M * 1000 + K + N)
+    if table == "8-bit":
+        bits = 8; lut = wl.make_lut(bits)
+    else:
+        bits = 6; lut = rng.integers(-2**20, 2**20, size=(64, 64)).astype(np.int32)
+    L = B.Lut(lut, bits)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x.flat[:4] = np.array([0.5, 1.5, 2.5, -0.5], np.float32)[: min(4, x.size)]      # ties, once the scale is 1
+    w = wl.random_i8(rng, (N, K), bits, "gauss")
+    bias = rng.standard_normal(N).astype(np.float32)
+    pw = B.adapt_weights_pack_linear(L, dev(w))
+    for s_x in (orc.scale_from_amax(orc.absmax(x), bits), np.float32(1.0)):
+        s_o = np.float32(s_x) * np.float32(0.01)
+        acc = orc.approx_linear(lut, bits, orc.quantize(x, s_x, bits), w, threads=orc.host_threads())
+        want = orc.relu(orc.dequant(acc, s_o, M, N, 1, bias)).reshape(M, N)
+        got = host(B.adapt_linear_layer_f32(pw, dev(x), s_x, s_o, bias=dev(bias), act=B.ACT_RELU))
+        assert bits_equal(got, want)
+        # the same matrix 4 bytes off a 16-byte boundary
+        buf = torch.empty(M * K + 1, dtype=torch.float32, device="cuda")
+        xm = buf[1:].view(M, K)
+        xm.copy_(dev(x))
+        got = host(B.adapt_linear_layer_f32(pw, xm, s_x, s_o, bias=dev(bias), act=B.ACT_RELU))
+        assert bits_equal(got, want)
+
+
 def test_config2_conv_full_size(B):
     c = wl.config2()
     bits = 8
