@@ -3,6 +3,8 @@ inputs.  Integer results must be bit-exact; fp32 results within 1e-6 relative (t
 produced by the same sequence of IEEE operations, and the elementwise tests check bit equality,
 because one differing ulp before a quantiser would flip an integer downstream).
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -44,6 +46,13 @@ def assert_f32_close(got, want):
 def bits_equal(a, b):
     a, b = np.ascontiguousarray(a, np.float32), np.ascontiguousarray(b, np.float32)
     return a.shape == b.shape and ((a.view(np.uint32) == b.view(np.uint32)) | ((a == 0) & (b == 0))).all()
+
+
+def seeds(*base):
+    """The seeds of a random-shape test: the fixed ones, plus ADAPT_EXTRA_SEEDS more (environment; default 0) for a longer
+    campaign, e.g. ADAPT_EXTRA_SEEDS=200 python -m pytest tests -m gpu -k random."""
+    extra = int(os.environ.get("ADAPT_EXTRA_SEEDS", "0"))
+    return list(base) + [1000 * base[0] + i for i in range(extra)]
 
 
 # ------------------------------------------------------------------ quantiser / dequantiser
@@ -1392,7 +1401,7 @@ def test_stored_small_cases(B):
 
 # ------------------------------------------------------------------ random shapes through every entry point
 
-@pytest.mark.parametrize("seed", [11, 12])
+@pytest.mark.parametrize("seed", seeds(11, 12))
 def test_random_shapes_match_oracle(B, seed):
     """Seeded random shapes (ragged sizes, strides, dilations, groups, table widths incl. a two-pass table, fused layer
     calls with bias / residual / activations, transposed convolutions, function multipliers) against the oracle: exercises
@@ -1510,7 +1519,7 @@ def test_random_shapes_match_oracle(B, seed):
     assert not bad, bad
 
 
-@pytest.mark.parametrize("seed", [41, 42])
+@pytest.mark.parametrize("seed", seeds(41, 42))
 def test_random_long_products_match_oracle(B, seed):
     """Seeded random shapes with thousands of rows and 16 to 128 channels - what the kernels that stream derived tables
     take, unsplit or with the inner dimension in slices: convolutions (filters 1 to 5 wide, vertical stride, dilation,
@@ -1580,7 +1589,7 @@ def test_random_long_products_match_oracle(B, seed):
     assert not bad, bad
 
 
-@pytest.mark.parametrize("seed", [21, 22])
+@pytest.mark.parametrize("seed", seeds(21, 22))
 def test_random_grouped_layers_match_oracle(B, seed):
     """Seeded random depthwise-style layers through the one-kernel layer call (fp32 in, scalar or per-channel output
     scale, bias, activation), half of them chained into a following 1x1 or 3x3 layer: y and the consumer's output
@@ -1918,7 +1927,7 @@ def test_quad_kernel_table_ranges(B, lo, span):
     assert bits_equal(host(B.adapt_conv2d_layer_f32(pw, dev(xf), s_x, np.float32(1e-6), (1, 1), (1, 1))), y)
 
 
-@pytest.mark.parametrize("seed", [31, 32])
+@pytest.mark.parametrize("seed", seeds(31, 32))
 def test_random_chains_match_oracle(B, seed):
     """Seeded random pairs of convolution layers, the first writing the second's quantised input copy in its epilogue:
     channel counts, image sizes, filter sizes, strides, paddings and table widths nobody picked by hand, so that every
